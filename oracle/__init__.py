@@ -1,0 +1,172 @@
+"""CPU oracle for BP-Transformer graph self-attention (test infrastructure only).
+
+This package wraps ``bpt_oracle.c`` -- a plain double-precision restatement of
+the paper's graph construction (Sec. 3.2), tree relative positions (Sec. 3.4)
+and graph self-attention (Sec. 3.1 eq. 6, Sec. 3.4 eq. 8) with its gradient.
+It exists to check the GPU library and to time a CPU baseline.  It shares no
+code with the HIP path and is never imported by the product package; only the
+tests, the smoke check and the benchmark's ``cpu_baseline`` leg may use it.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "bpt_oracle.c")
+_LIB = os.path.join(_HERE, "libbpt_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (OpenMP over batch*heads / rows)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-Wall", "-Wextra",
+             "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(_LIB)
+        i32, i64, f64 = ctypes.c_int32, ctypes.c_int64, ctypes.c_double
+        p = ctypes.c_void_p
+        L.bpto_num_levels.restype = i32
+        L.bpto_num_levels.argtypes = [i32]
+        L.bpto_level_offset.restype = i64
+        L.bpto_level_offset.argtypes = [i32, i32]
+        L.bpto_rel_width.restype = i32
+        L.bpto_rel_width.argtypes = [i32]
+        L.bpto_count_edges.restype = i64
+        L.bpto_count_edges.argtypes = [i32, i32, i32, p]
+        L.bpto_build_graph.restype = i32
+        L.bpto_build_graph.argtypes = [i32, i32, i32, p, p, p]
+        L.bpto_transpose.restype = None
+        L.bpto_transpose.argtypes = [i32, p, p, p, p, p]
+        L.bpto_attn_fwd.restype = i32
+        L.bpto_attn_fwd.argtypes = [i32, p, p, p, i32, i32, p, p, p, p, f64, p, p, i32]
+        L.bpto_attn_bwd.restype = i32
+        L.bpto_attn_bwd.argtypes = [i32, p, p, p, i32, i32, i32, p, p, p, p, p, f64, p, p, p, p, i32]
+        _lib = L
+    return _lib
+
+
+def _ptr(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+@dataclass
+class Graph:
+    """Binary-partition graph in CSR by query node (Sec. 3.2)."""
+    n: int
+    k: int
+    causal: bool
+    num_nodes: int          # 2n-1
+    num_levels: int         # log2(n)+1, tokens are level 0
+    rel_width: int          # W = 2(k+1)+1 slots per level in the r table
+    row_ptr: np.ndarray     # int32 [num_nodes+1]
+    col: np.ndarray         # int32 [E]  key node id
+    rel: np.ndarray         # int32 [E]  level*W + (offset + k+1)
+
+    @property
+    def num_edges(self) -> int:
+        return int(self.row_ptr[-1])
+
+    def level_offset(self, level: int) -> int:
+        return int(_load().bpto_level_offset(self.n, level))
+
+
+def num_levels(n: int) -> int:
+    return int(_load().bpto_num_levels(n))
+
+
+def level_offset(n: int, level: int) -> int:
+    return int(_load().bpto_level_offset(n, level))
+
+
+def degrees(n: int, k: int, causal: bool) -> np.ndarray:
+    L = _load()
+    deg = np.zeros(2 * n - 1, dtype=np.int64)
+    E = L.bpto_count_edges(n, k, int(causal), _ptr(deg))
+    if E < 0:
+        raise ValueError("n must be a power of two >= 2 and k >= 1")
+    return deg
+
+
+def build_graph(n: int, k: int, causal: bool) -> Graph:
+    L = _load()
+    E = L.bpto_count_edges(n, k, int(causal), None)
+    if E < 0:
+        raise ValueError("n must be a power of two >= 2 and k >= 1")
+    N = 2 * n - 1
+    row_ptr = np.zeros(N + 1, dtype=np.int32)
+    col = np.zeros(E, dtype=np.int32)
+    rel = np.zeros(E, dtype=np.int32)
+    rc = L.bpto_build_graph(n, k, int(causal), _ptr(row_ptr), _ptr(col), _ptr(rel))
+    if rc != 0:
+        raise RuntimeError("oracle graph build failed (edge count overflow?)")
+    return Graph(n, k, bool(causal), N, num_levels(n), int(L.bpto_rel_width(k)), row_ptr, col, rel)
+
+
+def transpose(g: Graph):
+    """(t_ptr, t_src, t_eid): for each key node its edges in ascending edge index."""
+    L = _load()
+    t_ptr = np.zeros(g.num_nodes + 1, dtype=np.int32)
+    t_src = np.zeros(g.num_edges, dtype=np.int32)
+    t_eid = np.zeros(g.num_edges, dtype=np.int32)
+    L.bpto_transpose(g.num_nodes, _ptr(g.row_ptr), _ptr(g.col), _ptr(t_ptr), _ptr(t_src), _ptr(t_eid))
+    return t_ptr, t_src, t_eid
+
+
+def _as_bhnd(x: np.ndarray, N: int):
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    if x.ndim != 4 or x.shape[2] != N:
+        raise ValueError("expected [B,H,N,D] with N=%d, got %r" % (N, x.shape))
+    return x
+
+
+def attn_fwd(g: Graph, Q, K, V, Rel, scale: float, threads: int = 0):
+    """Eq. (8) per node in float64.  Q,K,V: [B,H,N,D]; Rel: [levels,W,D].
+
+    Returns (out [B,H,N,D] f64, lse [B,H,N] f64, threads_used)."""
+    L = _load()
+    Q = _as_bhnd(Q, g.num_nodes)
+    K = _as_bhnd(K, g.num_nodes)
+    V = _as_bhnd(V, g.num_nodes)
+    B, H, N, D = Q.shape
+    Rel = np.ascontiguousarray(Rel, dtype=np.float32)
+    assert Rel.shape == (g.num_levels, g.rel_width, D), Rel.shape
+    out = np.zeros((B, H, N, D), dtype=np.float64)
+    lse = np.zeros((B, H, N), dtype=np.float64)
+    used = L.bpto_attn_fwd(N, _ptr(g.row_ptr), _ptr(g.col), _ptr(g.rel), B * H, D, _ptr(Q), _ptr(K),
+                           _ptr(V), _ptr(Rel), float(scale), _ptr(out), _ptr(lse), int(threads))
+    return out, lse, int(used)
+
+
+def attn_bwd(g: Graph, Q, K, V, Rel, dO, scale: float, threads: int = 0):
+    """Gradient of eq. (8) in float64.  Returns (dQ, dK, dV, dRel, threads_used)."""
+    L = _load()
+    Q = _as_bhnd(Q, g.num_nodes)
+    K = _as_bhnd(K, g.num_nodes)
+    V = _as_bhnd(V, g.num_nodes)
+    dO = _as_bhnd(dO, g.num_nodes)
+    B, H, N, D = Q.shape
+    Rel = np.ascontiguousarray(Rel, dtype=np.float32)
+    assert Rel.shape == (g.num_levels, g.rel_width, D), Rel.shape
+    dQ = np.zeros((B, H, N, D), dtype=np.float64)
+    dK = np.zeros_like(dQ)
+    dV = np.zeros_like(dQ)
+    dRel = np.zeros((g.num_levels, g.rel_width, D), dtype=np.float64)
+    used = L.bpto_attn_bwd(N, _ptr(g.row_ptr), _ptr(g.col), _ptr(g.rel), B * H, D,
+                           g.num_levels * g.rel_width, _ptr(Q), _ptr(K), _ptr(V), _ptr(Rel), _ptr(dO),
+                           float(scale), _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(dRel), int(threads))
+    return dQ, dK, dV, dRel, int(used)
