@@ -1,0 +1,164 @@
+#!/usr/bin/env python3
+"""Benchmark of the BP-Transformer graph self-attention hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload lm] [--no-cpu-baseline]
+
+A step is one forward + backward of graph self-attention (paper Sec. 3.1 eq. 6,
+Sec. 3.4 eq. 8) over one synthetic batch, on a graph built once beforehand by the
+GPU graph builder (Sec. 3.2) -- the graph depends only on (n, k, causal) and is
+shared by every layer, head and batch, so its build time is reported separately
+(`graph_build_ms`, and `edges_per_s_incl_build` charges one build to every step).
+Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
+FWD_BYTES_PER_EDGE = 256        # one K row + one V row (bf16, D=64) gathered per edge-instance
+BWD_Q_BYTES_PER_EDGE = 256      # query side of the backward: K row + V row again
+BWD_KV_BYTES_PER_EDGE = 256     # key side: Q row + dout row of the attending node
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="lm")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (--gpus 1); the path shards over (batch, head) "
+              "without communication, see DESIGN.md", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_1911_04070_amd import binding as bpt
+    from paper_1911_04070_amd.workloads import WORKLOADS, make_inputs
+
+    if not os.path.exists(bpt.LIB_PATH):
+        from paper_1911_04070_amd.build import build_library
+        build_library()
+    w = WORKLOADS[args.workload]
+    torch.cuda.set_device(0)
+    tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    bytes_scale = 1.0 if w.dtype == "bf16" else 2.0
+
+    x = make_inputs(w)
+    dev = {k: torch.from_numpy(v).to(tdt).cuda() for k, v in x.items()}
+
+    # graph build (GPU kernels + host schedule), timed on its own
+    torch.cuda.synchronize()
+    g = bpt.bpt_build_graph(w.n, w.k, w.causal)
+    g.destroy()
+    t0 = time.perf_counter()
+    g = bpt.bpt_build_graph(w.n, w.k, w.causal)
+    torch.cuda.synchronize()
+    build_ms = (time.perf_counter() - t0) * 1e3
+    edge_inst = w.B * w.H * g.num_edges
+
+    Q, K, V, R, dO = dev["Q"], dev["K"], dev["V"], dev["Rel"], dev["dO"]
+    out = torch.empty_like(Q)
+    lse = torch.empty(Q.shape[:3], dtype=torch.float32, device="cuda")
+    grads = tuple(torch.empty(Q.shape, dtype=torch.float32, device="cuda") for _ in range(3)) + (
+        torch.empty(R.shape, dtype=torch.float32, device="cuda"),)
+    fws, bws = bpt.workspace_bytes(g, Q, w.scale)
+    ws_f = torch.empty(max(fws, 256), dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(max(bws, 256), dtype=torch.uint8, device="cuda")
+
+    def step():
+        bpt.bpt_attn_fwd(g, Q, K, V, R, scale=w.scale, out=out, lse=lse, workspace=ws_f)
+        if w.backward:
+            bpt.bpt_attn_bwd(g, Q, K, V, R, lse, dO, scale=w.scale, grads=grads, workspace=ws_b)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # per-stage device time with events on the stream the library launches on
+    def timed(fn, reps):
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for a, b in evs:
+            a.record()
+            fn()
+            b.record()
+        torch.cuda.synchronize()
+        return float(np.mean([a.elapsed_time(b) for a, b in evs]))
+
+    reps = max(5, min(args.steps, 30))
+    stage_ms = {"fwd": timed(lambda: bpt.bpt_attn_fwd(g, Q, K, V, R, scale=w.scale, out=out, lse=lse,
+                                                      workspace=ws_f), reps)}
+    if w.backward:
+        stage_ms["bwd_query_side"] = timed(
+            lambda: bpt.bpt_attn_bwd_query_side(g, Q, K, V, R, lse, dO, grads[0], ws_b, scale=w.scale), reps)
+        stage_ms["bwd_key_side"] = timed(
+            lambda: bpt.bpt_attn_bwd_key_side(g, Q, K, V, R, lse, dO, grads[1], grads[2], grads[3], ws_b,
+                                              scale=w.scale), reps)
+    per_edge = {"fwd": FWD_BYTES_PER_EDGE, "bwd_query_side": BWD_Q_BYTES_PER_EDGE,
+                "bwd_key_side": BWD_KV_BYTES_PER_EDGE}
+    kernel_of = {"fwd": "fwd_kernel", "bwd_query_side": "bwd_q_kernel", "bwd_key_side": "bwd_kv_kernel"}
+    dominant = max(stage_ms, key=stage_ms.get)
+    achieved = per_edge[dominant] * bytes_scale * edge_inst / (stage_ms[dominant] * 1e-3) / 1e9
+    total_bytes = sum(per_edge[s] for s in stage_ms) * bytes_scale * edge_inst
+    roofline = {
+        "bound": "hbm", "kernel": kernel_of[dominant], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+        "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+        "launch_ms": round(stage_ms[dominant], 4),
+        "algorithmic_bytes_per_edge_instance": per_edge[dominant] * bytes_scale,
+        "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()},
+        "gathered_GBs_all_stages": round(total_bytes / (sum(stage_ms.values()) * 1e-3) / 1e9, 1),
+    }
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        og = oracle.build_graph(w.n, w.k, w.causal)
+        t0 = time.perf_counter()
+        _, _, used = oracle.attn_fwd(og, x["Q"], x["K"], x["V"], x["Rel"], w.scale)
+        if w.backward:
+            oracle.attn_bwd(og, x["Q"], x["K"], x["V"], x["Rel"], x["dO"], w.scale)
+        dt = time.perf_counter() - t0
+        cpu = {"value": round(edge_inst / dt, 1), "unit": "edges/s", "cores": used, "kind": "oracle",
+               "sample": "the whole workload once (forward%s), fp64, %.1f s" % (
+                   " + backward" if w.backward else "", dt)}
+
+    res = {
+        "metric": "BPT graph-attention fwd+bwd edges/sec" if w.backward else "BPT graph-attention fwd edges/sec",
+        "value": round(edge_inst / (ms_per_step * 1e-3), 1),
+        "unit": "edges/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "n": w.n, "k": w.k, "causal": w.causal, "batch": w.B, "heads": w.H,
+                   "head_dim": w.D, "nodes": g.num_nodes, "edges": g.num_edges, "edge_instances": edge_inst,
+                   "backward": w.backward},
+        "graph_build_ms": round(build_ms, 3),
+        "edges_per_s_incl_build": round(edge_inst / ((ms_per_step + build_ms) * 1e-3), 1),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(res), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,152 @@
+/*
+ * bpt.h -- C ABI of the MI355X (gfx950) BP-Transformer graph self-attention library.
+ *
+ * The library computes the hot path of BP-Transformer (arXiv 1911.04070):
+ *   1. the binary-partition graph of a sequence (Sec. 3.2): tokens are the
+ *      leaves of a perfect binary tree, spans its internal nodes; every span
+ *      node attends to the tokens it contains (affiliated edges) and every
+ *      token attends to itself and, per side and per tree level from fine to
+ *      coarse, to k (+1 alignment) nodes (contextual edges, Algorithm 1);
+ *   2. graph self-attention with tree relative positions over that graph
+ *      (Sec. 3.1 eq. (6), Sec. 3.4 eq. (8)), forward and backward.
+ *
+ * Conventions
+ *   - Every function returns a bpt_status_t code and never throws or aborts.
+ *   - "device" pointers are HIP device memory of the current device, owned by
+ *     the caller unless stated otherwise; "host" pointers are ordinary memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Attention calls are asynchronous on it.  bpt_build_graph and the
+ *     *_to_host calls synchronise it.
+ *   - Nodes are numbered level-major: id(l,m) = 2n - (2n >> l) + m, so tokens
+ *     are 0..n-1, level-1 spans n..n+n/2-1, ..., the root is 2n-2.  N = 2n-1.
+ *   - An edge u <- v ("u attends to v") is stored in row u of a CSR
+ *     (row_ptr[N+1], col[E] = v, rel[E] = relative-position id).  The id packs
+ *     (level j of v, signed order o) as  j*W + (o + k+1),  W = 2(k+1)+1:
+ *     o = 0 at level 0 is r_self, o = 0 at level j>=1 is r_anc(j) (span rows),
+ *     o = +i / -i is the i-th node to join on the right / left at level j,
+ *     nearest first, i = 1..k+1 (Sec. 3.4).  Rows are sorted by id ascending
+ *     (which also sorts them by col).
+ *   - The relative-position table `rel` is [num_levels][W][D] in the tensor
+ *     dtype, shared by all batches and heads (Sec. 3.4).
+ *   - Q, K, V, out, dout and the fp32 gradients dQ, dK, dV are [B][H][N][D]
+ *     with D contiguous and element strides stride_b, stride_h, stride_n
+ *     (the same for all of them); lse is contiguous [B][H][N] fp32.
+ *   - Outputs are fully overwritten, never accumulated into.
+ */
+#ifndef BPT_H_
+#define BPT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct bpt_graph bpt_graph_t; /* opaque; device-resident; owned by the library */
+
+typedef enum { BPT_F32 = 0, BPT_BF16 = 1 } bpt_dtype_t;
+
+typedef enum {
+    BPT_OK = 0,
+    BPT_ERR_INVALID_ARG = 1, /* null pointer, k < 1, n < 2, bad stride, small workspace */
+    BPT_ERR_UNSUPPORTED = 2, /* n not a power of two, n > 2^22, k > 2^20, D != 64, dtype */
+    BPT_ERR_ALLOC = 3,       /* device or host allocation failed */
+    BPT_ERR_LAUNCH = 4,      /* a HIP call or kernel launch failed */
+    BPT_ERR_OVERFLOW = 5     /* the graph has more than INT32_MAX edges */
+} bpt_status_t;
+
+typedef struct {
+    int32_t B, H, D;     /* batch, heads, head width (D must be 64) */
+    int32_t dtype;       /* bpt_dtype_t of Q, K, V, rel, out, dout */
+    int64_t stride_b, stride_h, stride_n; /* in elements; stride_n >= D, multiples of 8 */
+    float scale;         /* softmax scale; <= 0 selects 1/sqrt(D) (Sec. 3.1 eq. (6)) */
+} bpt_shape_t;
+
+/* Sec. 3.2 + Algorithm 1.  Builds, on the current device, the graph of a
+ * sequence of n tokens (power of two, 2 <= n <= 2^22) with density k
+ * (1 <= k <= 2^20): CSR by query node, its transposed adjacency, and the launch
+ * schedules the attention kernels use.  causal != 0 drops every token's right
+ * context (left contexts only).  All edges are produced by GPU kernels; the
+ * result is bit-identical to a sequential CPU construction.  *out is owned by
+ * the library until bpt_graph_destroy.  Synchronises `stream`. */
+int bpt_build_graph(int32_t n, int32_t k, int32_t causal, void* stream, bpt_graph_t** out);
+
+/* Any output pointer may be NULL.  num_levels = log2(n)+1, rel_width = W,
+ * ctx_levels = number of levels on which some token has contextual nodes. */
+int bpt_graph_info(const bpt_graph_t* g, int32_t* n, int32_t* k, int32_t* causal,
+                   int32_t* num_nodes, int64_t* num_edges, int32_t* num_levels,
+                   int32_t* rel_width, int32_t* ctx_levels);
+
+/* Device pointers into the graph, valid until destroy: row_ptr[N+1], col[E], rel[E]. */
+int bpt_graph_csr(const bpt_graph_t* g, const int32_t** row_ptr, const int32_t** col,
+                  const int32_t** rel);
+
+/* Transposed adjacency (device pointers): for each key node v, t_ptr[v]..t_ptr[v+1]
+ * lists the edges that point at it in ascending edge index: t_src = query node,
+ * t_eid = index of the edge in col/rel. */
+int bpt_graph_transposed(const bpt_graph_t* g, const int32_t** t_ptr, const int32_t** t_src,
+                         const int32_t** t_eid);
+
+/* Copies to host arrays the caller allocated (sizes as above); NULL skips one. */
+int bpt_graph_to_host(const bpt_graph_t* g, int32_t* row_ptr, int32_t* col, int32_t* rel);
+int bpt_graph_transposed_to_host(const bpt_graph_t* g, int32_t* t_ptr, int32_t* t_src,
+                                 int32_t* t_eid);
+
+void bpt_graph_destroy(bpt_graph_t* g);
+
+/* Bytes of device scratch the forward / backward need for this graph and shape
+ * (0 is possible).  The caller allocates it (256-byte aligned) and may reuse it
+ * between calls on the same stream. */
+size_t bpt_attn_fwd_workspace(const bpt_graph_t* g, const bpt_shape_t* s);
+size_t bpt_attn_bwd_workspace(const bpt_graph_t* g, const bpt_shape_t* s);
+
+/* Sec. 3.4 eq. (8), for every node u of every (batch, head):
+ *   s_e   = scale * q_u . (k_v + rel[id_e])        over the edges e = (u <- v) of row u
+ *   lse_u = log sum_e exp(s_e)                      (natural log)
+ *   out_u = sum_e exp(s_e - lse_u) * v_v
+ * Arithmetic is fp32 whatever the storage dtype.  Q, K, V, rel: device, read only.
+ * out (tensor dtype) and lse (fp32): device, written.  workspace: device scratch
+ * of at least bpt_attn_fwd_workspace bytes (may be NULL when that is 0). */
+int bpt_attn_fwd(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q, const void* K,
+                 const void* V, const void* rel, void* out, float* lse, void* workspace,
+                 size_t workspace_bytes, void* stream);
+
+/* Gradient of eq. (8) given dout = dL/dout.  With p_e = exp(s_e - lse_u),
+ * dP_e = dout_u . v_v, delta_u = sum_e p_e dP_e (= dout_u . out_u), dS_e = p_e (dP_e - delta_u):
+ *   dQ_u = scale * sum_e dS_e (k_v + rel[id_e])
+ *   dK_v = scale * sum_{e -> v} dS_e q_u        dV_v = sum_{e -> v} p_e dout_u
+ *   d_rel[id] = scale * sum over batch, head and edges with id_e = id of dS_e q_u
+ * lse is the forward's result; the forward's `out` is not needed (delta is
+ * recomputed in fp32 from p and dP).  dQ, dK, dV (fp32, the tensor strides) and
+ * d_rel (fp32, contiguous [num_levels][W][D]) are overwritten.  dQ, dK and dV are
+ * run-to-run identical (dK, dV are reduced over the transposed adjacency, no
+ * atomics); d_rel is accumulated with fp32 atomics in on-chip memory and is
+ * reproducible only up to rounding order.  workspace: device scratch of at least
+ * bpt_attn_bwd_workspace bytes. */
+int bpt_attn_bwd(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q, const void* K,
+                 const void* V, const void* rel, const float* lse, const void* dout, float* dQ,
+                 float* dK, float* dV, float* d_rel, void* workspace, size_t workspace_bytes,
+                 void* stream);
+
+/* The two stages of bpt_attn_bwd, callable on their own (same workspace, same
+ * stream order): the query side walks the CSR rows and produces dQ and, in the
+ * workspace, delta; the key side walks the transposed adjacency, reads that delta
+ * and produces dK, dV and d_rel.  bpt_attn_bwd is exactly the first followed by
+ * the second. */
+int bpt_attn_bwd_query_side(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q,
+                            const void* K, const void* V, const void* rel, const float* lse,
+                            const void* dout, float* dQ, void* workspace, size_t workspace_bytes,
+                            void* stream);
+int bpt_attn_bwd_key_side(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q,
+                          const void* K, const void* V, const void* rel, const float* lse,
+                          const void* dout, float* dK, float* dV, float* d_rel, void* workspace,
+                          size_t workspace_bytes, void* stream);
+
+/* Static, never NULL. */
+const char* bpt_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BPT_H_ */

@@ -1,0 +1,278 @@
+"""ctypes binding of libbpt.so (the C ABI declared in include/bpt.h).
+
+Argument marshalling only: every step of the path runs in the library's HIP
+kernels.  torch supplies device memory and the stream, nothing else.  There is
+no CPU fallback: a missing library is an error.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libbpt.so")
+
+BPT_F32, BPT_BF16 = 0, 1
+BPT_OK, BPT_ERR_INVALID_ARG, BPT_ERR_UNSUPPORTED, BPT_ERR_ALLOC, BPT_ERR_LAUNCH, BPT_ERR_OVERFLOW = range(6)
+
+EXPORTS = [
+    "bpt_build_graph", "bpt_graph_info", "bpt_graph_csr", "bpt_graph_transposed", "bpt_graph_to_host",
+    "bpt_graph_transposed_to_host", "bpt_graph_destroy", "bpt_attn_fwd_workspace", "bpt_attn_bwd_workspace",
+    "bpt_attn_fwd", "bpt_attn_bwd", "bpt_attn_bwd_query_side", "bpt_attn_bwd_key_side", "bpt_strerror",
+]
+
+
+class BptShape(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("D", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64), ("stride_n", ctypes.c_int64),
+                ("scale", ctypes.c_float)]
+
+
+class BptError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (what, strerror(status), status))
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Loads the in-tree libbpt.so; building it is __graft_entry__.build()'s job."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            "%s is missing: build it with `python -m paper_1911_04070_amd.build` "
+            "(there is no CPU fallback)" % LIB_PATH)
+    L = ctypes.CDLL(LIB_PATH)
+    i32, i64, vp, sz = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t
+    P = ctypes.POINTER
+    L.bpt_build_graph.restype = ctypes.c_int
+    L.bpt_build_graph.argtypes = [i32, i32, i32, vp, P(vp)]
+    L.bpt_graph_info.restype = ctypes.c_int
+    L.bpt_graph_info.argtypes = [vp, P(i32), P(i32), P(i32), P(i32), P(i64), P(i32), P(i32), P(i32)]
+    L.bpt_graph_csr.restype = ctypes.c_int
+    L.bpt_graph_csr.argtypes = [vp, P(vp), P(vp), P(vp)]
+    L.bpt_graph_transposed.restype = ctypes.c_int
+    L.bpt_graph_transposed.argtypes = [vp, P(vp), P(vp), P(vp)]
+    L.bpt_graph_to_host.restype = ctypes.c_int
+    L.bpt_graph_to_host.argtypes = [vp, vp, vp, vp]
+    L.bpt_graph_transposed_to_host.restype = ctypes.c_int
+    L.bpt_graph_transposed_to_host.argtypes = [vp, vp, vp, vp]
+    L.bpt_graph_destroy.restype = None
+    L.bpt_graph_destroy.argtypes = [vp]
+    L.bpt_attn_fwd_workspace.restype = sz
+    L.bpt_attn_fwd_workspace.argtypes = [vp, P(BptShape)]
+    L.bpt_attn_bwd_workspace.restype = sz
+    L.bpt_attn_bwd_workspace.argtypes = [vp, P(BptShape)]
+    L.bpt_attn_fwd.restype = ctypes.c_int
+    L.bpt_attn_fwd.argtypes = [vp, P(BptShape), vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.bpt_attn_bwd.restype = ctypes.c_int
+    L.bpt_attn_bwd.argtypes = [vp, P(BptShape)] + [vp] * 11 + [sz, vp]
+    L.bpt_attn_bwd_query_side.restype = ctypes.c_int
+    L.bpt_attn_bwd_query_side.argtypes = [vp, P(BptShape)] + [vp] * 8 + [sz, vp]
+    L.bpt_attn_bwd_key_side.restype = ctypes.c_int
+    L.bpt_attn_bwd_key_side.argtypes = [vp, P(BptShape)] + [vp] * 10 + [sz, vp]
+    L.bpt_strerror.restype = ctypes.c_char_p
+    L.bpt_strerror.argtypes = [ctypes.c_int]
+    _lib = L
+    return L
+
+
+def strerror(status: int) -> str:
+    return load_library().bpt_strerror(int(status)).decode()
+
+
+def _check(status: int, what: str) -> None:
+    if status != BPT_OK:
+        raise BptError(status, what)
+
+
+def _stream_ptr() -> int:
+    return int(torch.cuda.current_stream().cuda_stream)
+
+
+class Graph:
+    """Device-resident binary-partition graph (bpt_build_graph)."""
+
+    def __init__(self, n: int, k: int, causal: bool):
+        L = load_library()
+        handle = ctypes.c_void_p()
+        _check(L.bpt_build_graph(int(n), int(k), int(bool(causal)), _stream_ptr(), ctypes.byref(handle)),
+               "bpt_build_graph(n=%d, k=%d, causal=%d)" % (n, k, causal))
+        self._h = handle
+        i32, i64 = ctypes.c_int32, ctypes.c_int64
+        vals = [i32(), i32(), i32(), i32(), i64(), i32(), i32(), i32()]
+        _check(L.bpt_graph_info(self._h, *[ctypes.byref(v) for v in vals]), "bpt_graph_info")
+        (self.n, self.k, causal_i, self.num_nodes, self.num_edges, self.num_levels, self.rel_width,
+         self.ctx_levels) = [int(v.value) for v in vals]
+        self.causal = bool(causal_i)
+
+    @property
+    def handle(self) -> ctypes.c_void_p:
+        if self._h is None:
+            raise RuntimeError("graph was destroyed")
+        return self._h
+
+    def destroy(self) -> None:
+        if getattr(self, "_h", None) is not None:
+            load_library().bpt_graph_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    def csr_to_host(self) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+        row_ptr = np.empty(self.num_nodes + 1, dtype=np.int32)
+        col = np.empty(self.num_edges, dtype=np.int32)
+        rel = np.empty(self.num_edges, dtype=np.int32)
+        _check(load_library().bpt_graph_to_host(self.handle, row_ptr.ctypes.data, col.ctypes.data, rel.ctypes.data),
+               "bpt_graph_to_host")
+        return row_ptr, col, rel
+
+    def transposed_to_host(self) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+        t_ptr = np.empty(self.num_nodes + 1, dtype=np.int32)
+        t_src = np.empty(self.num_edges, dtype=np.int32)
+        t_eid = np.empty(self.num_edges, dtype=np.int32)
+        _check(load_library().bpt_graph_transposed_to_host(self.handle, t_ptr.ctypes.data, t_src.ctypes.data,
+                                                           t_eid.ctypes.data), "bpt_graph_transposed_to_host")
+        return t_ptr, t_src, t_eid
+
+    def device_pointers(self) -> dict:
+        L = load_library()
+        a, b, c = ctypes.c_void_p(), ctypes.c_void_p(), ctypes.c_void_p()
+        _check(L.bpt_graph_csr(self.handle, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)), "bpt_graph_csr")
+        d, e, f = ctypes.c_void_p(), ctypes.c_void_p(), ctypes.c_void_p()
+        _check(L.bpt_graph_transposed(self.handle, ctypes.byref(d), ctypes.byref(e), ctypes.byref(f)),
+               "bpt_graph_transposed")
+        return {"row_ptr": a.value, "col": b.value, "rel": c.value, "t_ptr": d.value, "t_src": e.value,
+                "t_eid": f.value}
+
+
+def bpt_build_graph(n: int, k: int, causal: bool) -> Graph:
+    return Graph(n, k, causal)
+
+
+def _shape_of(g: Graph, x: torch.Tensor, scale: Optional[float]) -> BptShape:
+    if x.dim() != 4 or x.shape[2] != g.num_nodes:
+        raise ValueError("expected a [B,H,N=%d,D] tensor, got %s" % (g.num_nodes, tuple(x.shape)))
+    if x.stride(3) != 1:
+        raise ValueError("the feature dimension must be contiguous")
+    if x.dtype == torch.float32:
+        dt = BPT_F32
+    elif x.dtype == torch.bfloat16:
+        dt = BPT_BF16
+    else:
+        raise ValueError("dtype must be float32 or bfloat16")
+    B, H, _, D = x.shape
+    return BptShape(B, H, D, dt, x.stride(0), x.stride(1), x.stride(2), float(scale) if scale else 0.0)
+
+
+def _same_layout(ref: torch.Tensor, *others: torch.Tensor) -> None:
+    for t in others:
+        if t.shape != ref.shape or t.stride() != ref.stride() or t.device != ref.device:
+            raise ValueError("tensors must share shape, strides and device")
+
+
+def _workspace(nbytes: int, device) -> Tuple[Optional[torch.Tensor], int]:
+    if nbytes == 0:
+        return None, 0
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    return ws, ws.data_ptr()
+
+
+def bpt_attn_fwd(g: Graph, Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, rel: torch.Tensor,
+                 scale: Optional[float] = None, out: Optional[torch.Tensor] = None,
+                 lse: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None):
+    """out, lse = graph attention of eq. (8).  Q,K,V: [B,H,N,D] cuda tensors; rel: [levels,W,D]."""
+    L = load_library()
+    shp = _shape_of(g, Q, scale)
+    _same_layout(Q, K, V)
+    if K.dtype != Q.dtype or V.dtype != Q.dtype or rel.dtype != Q.dtype:
+        raise ValueError("Q, K, V and rel must share a dtype")
+    if tuple(rel.shape) != (g.num_levels, g.rel_width, shp.D) or not rel.is_contiguous():
+        raise ValueError("rel must be contiguous [%d,%d,%d]" % (g.num_levels, g.rel_width, shp.D))
+    if out is None:
+        out = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
+    if lse is None:
+        lse = torch.empty(Q.shape[:3], dtype=torch.float32, device=Q.device)
+    _same_layout(Q, out)
+    need = int(L.bpt_attn_fwd_workspace(g.handle, ctypes.byref(shp)))
+    if workspace is None:
+        workspace, ws_ptr = _workspace(need, Q.device)
+    else:
+        ws_ptr = workspace.data_ptr()
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(L.bpt_attn_fwd(g.handle, ctypes.byref(shp), Q.data_ptr(), K.data_ptr(), V.data_ptr(), rel.data_ptr(),
+                          out.data_ptr(), lse.data_ptr(), ws_ptr, ws_bytes, _stream_ptr()), "bpt_attn_fwd")
+    return out, lse
+
+
+def _bwd_prepare(g, Q, K, V, rel, lse, dout, scale, grads, workspace):
+    L = load_library()
+    shp = _shape_of(g, Q, scale)
+    _same_layout(Q, K, V, dout)
+    if lse.dtype != torch.float32 or tuple(lse.shape) != tuple(Q.shape[:3]) or not lse.is_contiguous():
+        raise ValueError("lse must be contiguous fp32 [B,H,N]")
+    if grads is None:
+        dQ, dK, dV = (torch.empty_strided(Q.shape, Q.stride(), dtype=torch.float32, device=Q.device)
+                      for _ in range(3))
+        d_rel = torch.empty((g.num_levels, g.rel_width, shp.D), dtype=torch.float32, device=Q.device)
+    else:
+        dQ, dK, dV, d_rel = grads
+    _same_layout(Q, dQ, dK, dV)
+    need = int(L.bpt_attn_bwd_workspace(g.handle, ctypes.byref(shp)))
+    if workspace is None:
+        workspace, _ = _workspace(need, Q.device)
+    ws_bytes = workspace.numel() * workspace.element_size()
+    return L, shp, (dQ, dK, dV, d_rel), workspace, ws_bytes
+
+
+def bpt_attn_bwd(g: Graph, Q, K, V, rel, lse, dout, scale: Optional[float] = None,
+                 grads: Optional[Tuple[torch.Tensor, ...]] = None, workspace: Optional[torch.Tensor] = None):
+    """dQ, dK, dV, d_rel (all fp32) = gradient of eq. (8) given dout and the forward's lse."""
+    L, shp, (dQ, dK, dV, d_rel), ws, ws_bytes = _bwd_prepare(g, Q, K, V, rel, lse, dout, scale, grads, workspace)
+    _check(L.bpt_attn_bwd(g.handle, ctypes.byref(shp), Q.data_ptr(), K.data_ptr(), V.data_ptr(), rel.data_ptr(),
+                          lse.data_ptr(), dout.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(),
+                          d_rel.data_ptr(), ws.data_ptr(), ws_bytes, _stream_ptr()), "bpt_attn_bwd")
+    return dQ, dK, dV, d_rel
+
+
+def bpt_attn_bwd_query_side(g: Graph, Q, K, V, rel, lse, dout, dQ, workspace, scale: Optional[float] = None):
+    """First stage of the backward: dQ, and delta into the workspace."""
+    L = load_library()
+    shp = _shape_of(g, Q, scale)
+    _check(L.bpt_attn_bwd_query_side(g.handle, ctypes.byref(shp), Q.data_ptr(), K.data_ptr(), V.data_ptr(),
+                                     rel.data_ptr(), lse.data_ptr(), dout.data_ptr(), dQ.data_ptr(),
+                                     workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                     _stream_ptr()), "bpt_attn_bwd_query_side")
+    return dQ
+
+
+def bpt_attn_bwd_key_side(g: Graph, Q, K, V, rel, lse, dout, dK, dV, d_rel, workspace,
+                          scale: Optional[float] = None):
+    """Second stage of the backward: dK, dV, d_rel (reads delta from the workspace)."""
+    L = load_library()
+    shp = _shape_of(g, Q, scale)
+    _check(L.bpt_attn_bwd_key_side(g.handle, ctypes.byref(shp), Q.data_ptr(), K.data_ptr(), V.data_ptr(),
+                                   rel.data_ptr(), lse.data_ptr(), dout.data_ptr(), dK.data_ptr(), dV.data_ptr(),
+                                   d_rel.data_ptr(), workspace.data_ptr(),
+                                   workspace.numel() * workspace.element_size(), _stream_ptr()),
+           "bpt_attn_bwd_key_side")
+    return dK, dV, d_rel
+
+
+def workspace_bytes(g: Graph, like: torch.Tensor, scale: Optional[float] = None) -> Tuple[int, int]:
+    L = load_library()
+    shp = _shape_of(g, like, scale)
+    return (int(L.bpt_attn_fwd_workspace(g.handle, ctypes.byref(shp))),
+            int(L.bpt_attn_bwd_workspace(g.handle, ctypes.byref(shp))))

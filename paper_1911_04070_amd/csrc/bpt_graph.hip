@@ -1,0 +1,610 @@
+// Binary-partition graph construction on the GPU (paper Sec. 3.2, Algorithm 1)
+// plus the host-side launch schedules of the attention kernels.
+//
+// Kernels (all integer work, results independent of thread order):
+//   token_degree   one thread per token runs the contextual-node recurrence and counts
+//   scan_*         exclusive prefix sum -> row_ptr
+//   fill_tokens    one thread per token emits (col, rel) of its row in canonical order
+//   fill_spans     one thread per affiliated edge (closed form)
+//   t_count        per token-row edge: in-degree and first query on each side of the key
+//   t_fill         closed-form slot of every edge in the transposed adjacency
+#include <algorithm>
+#include <new>
+#include <vector>
+
+#include "bpt_internal.h"
+
+namespace bpt {
+namespace {
+
+constexpr int kScanThreads = 256;
+constexpr int kScanItems = 16;
+constexpr int kScanBlock = kScanThreads * kScanItems;  // elements per block
+
+__host__ __device__ inline int64_t level_offset(int64_t n, int level) { return 2 * n - ((2 * n) >> level); }
+
+// One side's walk over the tree levels for token i (Sec. 3.2.2, contextual
+// edges): at level j the run covers the nodes [lo, hi]; `near` is the end next to
+// the token.  k nodes per level; the run is clipped to the level and grows by
+// one node when it would not end on a parent boundary, so that the next level
+// starts exactly where this one ends.
+struct LeftWalk {
+    int q;  // nearest node of the current level; < 0 when the side is exhausted
+    __device__ explicit LeftWalk(int i) : q(i - 1) {}
+    __device__ bool alive() const { return q >= 0; }
+    __device__ void run(int k, int& lo, int& hi) const {
+        int e = q - k + 1;  // k <= 2^20 and q < 2^22: no overflow
+        if (e < 0) e = 0;
+        if (e & 1) e -= 1;  // ends on a right child: its sibling joins
+        lo = e;
+        hi = q;
+    }
+    __device__ void up(int lo) { q = (lo - 1 < 0) ? -1 : ((lo - 1) >> 1); }
+};
+
+struct RightWalk {
+    int p, size;  // nearest node and node count of the current level
+    __device__ RightWalk(int i, int n) : p(i + 1), size(n) {}
+    __device__ bool alive() const { return p < size; }
+    __device__ void run(int k, int& lo, int& hi) const {
+        int e = (k - 1 > size - 1 - p) ? size - 1 : p + k - 1;  // min(p+k-1, size-1) without overflow
+        if ((e & 1) == 0) e += 1;  // ends on a left child: its sibling joins (size is even)
+        lo = p;
+        hi = e;
+    }
+    __device__ void up(int hi) {
+        int nxt = hi + 1;
+        if (nxt >= size) {
+            p = size;  // exhausted
+        } else {
+            p = nxt >> 1;
+            size >>= 1;
+        }
+    }
+};
+
+__global__ void token_degree(int n, int k, int causal, int32_t* __restrict__ deg,
+                             unsigned long long* __restrict__ total, int32_t* __restrict__ max_levels) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    int d = 0, used = 0;
+    if (i < n) {
+        d = 1;  // self (Algorithm 1 starts from N = {u})
+        LeftWalk L(i);
+        int lv = 0;
+        while (L.alive()) {
+            int lo, hi;
+            L.run(k, lo, hi);
+            d += hi - lo + 1;
+            L.up(lo);
+            ++lv;
+        }
+        used = lv;
+        if (!causal) {
+            RightWalk R(i, n);
+            lv = 0;
+            while (R.alive()) {
+                int lo, hi;
+                R.run(k, lo, hi);
+                d += hi - lo + 1;
+                R.up(hi);
+                ++lv;
+            }
+            used = max(used, lv);
+        }
+        deg[i] = d;
+    }
+    // block totals -> one 64-bit atomic per block (integer: order does not matter)
+    __shared__ unsigned long long s_sum[kScanThreads];
+    __shared__ int s_lv[kScanThreads];
+    s_sum[threadIdx.x] = (unsigned long long)d;
+    s_lv[threadIdx.x] = used;
+    __syncthreads();
+    for (int w = blockDim.x / 2; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) {
+            s_sum[threadIdx.x] += s_sum[threadIdx.x + w];
+            s_lv[threadIdx.x] = max(s_lv[threadIdx.x], s_lv[threadIdx.x + w]);
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        atomicAdd(total, s_sum[0]);
+        atomicMax(max_levels, s_lv[0]);
+    }
+}
+
+// ---- exclusive scan of int32 (three phases) ------------------------------
+__global__ void scan_blocks(const int32_t* __restrict__ in, int32_t* __restrict__ out, int32_t* __restrict__ block_sums,
+                            int m) {
+    __shared__ int32_t s[kScanThreads];
+    int base = blockIdx.x * kScanBlock + threadIdx.x * kScanItems;
+    int32_t v[kScanItems];
+    int32_t sum = 0;
+#pragma unroll
+    for (int j = 0; j < kScanItems; ++j) {
+        int idx = base + j;
+        v[j] = idx < m ? in[idx] : 0;
+        sum += v[j];
+    }
+    s[threadIdx.x] = sum;
+    __syncthreads();
+    for (int off = 1; off < kScanThreads; off <<= 1) {  // inclusive scan of the thread sums
+        int32_t t = (int)threadIdx.x >= off ? s[threadIdx.x - off] : 0;
+        __syncthreads();
+        s[threadIdx.x] += t;
+        __syncthreads();
+    }
+    int32_t run = s[threadIdx.x] - sum;  // exclusive prefix of this thread inside the block
+#pragma unroll
+    for (int j = 0; j < kScanItems; ++j) {
+        int idx = base + j;
+        if (idx < m) out[idx] = run;
+        run += v[j];
+    }
+    if (threadIdx.x == kScanThreads - 1) block_sums[blockIdx.x] = s[threadIdx.x];
+}
+
+__global__ void scan_sums(int32_t* __restrict__ block_sums, int nblocks) {  // one block, nblocks <= kScanBlock
+    __shared__ int32_t s[kScanThreads];
+    int base = threadIdx.x * kScanItems;
+    int32_t v[kScanItems];
+    int32_t sum = 0;
+#pragma unroll
+    for (int j = 0; j < kScanItems; ++j) {
+        v[j] = base + j < nblocks ? block_sums[base + j] : 0;
+        sum += v[j];
+    }
+    s[threadIdx.x] = sum;
+    __syncthreads();
+    for (int off = 1; off < kScanThreads; off <<= 1) {
+        int32_t t = (int)threadIdx.x >= off ? s[threadIdx.x - off] : 0;
+        __syncthreads();
+        s[threadIdx.x] += t;
+        __syncthreads();
+    }
+    int32_t run = s[threadIdx.x] - sum;
+#pragma unroll
+    for (int j = 0; j < kScanItems; ++j) {
+        if (base + j < nblocks) block_sums[base + j] = run;
+        run += v[j];
+    }
+}
+
+__global__ void scan_add(int32_t* __restrict__ out, const int32_t* __restrict__ block_sums, int m, int32_t total) {
+    int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx < m) out[idx] += block_sums[idx / kScanBlock];
+    if (idx == m) out[m] = total;
+}
+
+// ---- CSR fill ---------------------------------------------------------------
+__global__ void fill_tokens(int n, int k, int causal, const int32_t* __restrict__ row_ptr, int32_t* __restrict__ col,
+                            int32_t* __restrict__ rel) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const int W = 2 * (k + 1) + 1, zero = k + 1;
+    int e = row_ptr[i];
+    LeftWalk L(i);
+    RightWalk R(i, causal ? 0 : n);  // size 0: never alive
+    for (int j = 0; j == 0 || L.alive() || R.alive(); ++j) {
+        const int off = (int)level_offset(n, j);
+        if (L.alive()) {  // far -> near: orders -(count) .. -1
+            int lo, hi;
+            L.run(k, lo, hi);
+            for (int x = lo; x <= hi; ++x) {
+                col[e] = off + x;
+                rel[e] = j * W + zero - (hi - x + 1);
+                ++e;
+            }
+            L.up(lo);
+        }
+        if (j == 0) {  // self, r_self
+            col[e] = i;
+            rel[e] = zero;
+            ++e;
+        }
+        if (R.alive()) {  // near -> far: orders +1 .. +count
+            int lo, hi;
+            R.run(k, lo, hi);
+            for (int x = lo; x <= hi; ++x) {
+                col[e] = off + x;
+                rel[e] = j * W + zero + (x - lo + 1);
+                ++e;
+            }
+            R.up(hi);
+        }
+    }
+}
+
+// Affiliated edges (Sec. 3.2.2): span (l,m) <- tokens m*2^l .. (m+1)*2^l-1.  The
+// n edges of one level are simply the tokens 0..n-1 in order.
+__global__ void fill_spans(int n, int k, int num_levels, int32_t e_tok, int32_t* __restrict__ row_ptr,
+                           int32_t* __restrict__ col, int32_t* __restrict__ rel) {
+    const int64_t a = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t total = (int64_t)n * (num_levels - 1);
+    const int W = 2 * (k + 1) + 1, zero = k + 1;
+    if (a < total) {
+        int lev = 1 + (int)(a / n);
+        int t = (int)(a % n);
+        col[e_tok + a] = t;
+        rel[e_tok + a] = lev * W + zero;  // r_anc(lev)
+    }
+    if (a < n - 1) {  // span row starts: a-th span node in level-major order
+        int64_t node = n + a;
+        int64_t x = 2 * (int64_t)n - node;                 // (n >> l) < x <= (2n >> l)
+        int ceil_log2 = 64 - __clzll((unsigned long long)(x - 1));
+        int lev = num_levels - ceil_log2;                  // log2(2n) = num_levels
+        int64_t m = node - level_offset(n, lev);
+        row_ptr[node] = (int32_t)(e_tok + (int64_t)(lev - 1) * n + (m << lev));
+    }
+    if (a == 0) row_ptr[2 * n - 1] = (int32_t)(e_tok + total);
+}
+
+// ---- transposed adjacency -----------------------------------------------------
+// For a key node v the tokens attending to it from its left (they see v in their
+// right context) form one contiguous range, and so do those on its right: the run
+// boundaries of the walks above are monotone in the token index.  So the slot of
+// an edge in v's list follows from counts and range starts alone.
+__global__ void t_init(int num_nodes, int32_t* __restrict__ cnt_l, int32_t* __restrict__ cnt_r,
+                       int32_t* __restrict__ min_l, int32_t* __restrict__ min_r) {
+    int v = blockIdx.x * blockDim.x + threadIdx.x;
+    if (v < num_nodes) {
+        cnt_l[v] = 0;
+        cnt_r[v] = 0;
+        min_l[v] = INT32_MAX;
+        min_r[v] = INT32_MAX;
+    }
+}
+
+__global__ void t_count(int n, int k, const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col,
+                        const int32_t* __restrict__ rel, int32_t* __restrict__ cnt_l, int32_t* __restrict__ cnt_r,
+                        int32_t* __restrict__ min_l, int32_t* __restrict__ min_r) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const int W = 2 * (k + 1) + 1, zero = k + 1;
+    for (int e = row_ptr[i]; e < row_ptr[i + 1]; ++e) {
+        int order = rel[e] % W - zero;
+        int v = col[e];
+        if (order > 0) {  // v lies to the right of token i: i is a query on v's left
+            atomicAdd(&cnt_l[v], 1);
+            atomicMin(&min_l[v], i);
+        } else if (order < 0) {
+            atomicAdd(&cnt_r[v], 1);
+            atomicMin(&min_r[v], i);
+        }
+    }
+}
+
+__global__ void t_degree(int n, int num_nodes, int num_levels, const int32_t* __restrict__ cnt_l,
+                         const int32_t* __restrict__ cnt_r, int32_t* __restrict__ t_deg) {
+    int v = blockIdx.x * blockDim.x + threadIdx.x;
+    if (v < num_nodes) t_deg[v] = cnt_l[v] + cnt_r[v] + (v < n ? num_levels : 0);  // self + one per ancestor
+}
+
+__global__ void t_fill_tokens(int n, int k, const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col,
+                              const int32_t* __restrict__ rel, const int32_t* __restrict__ t_ptr,
+                              const int32_t* __restrict__ cnt_l, const int32_t* __restrict__ min_l,
+                              const int32_t* __restrict__ min_r, int32_t* __restrict__ t_src,
+                              int32_t* __restrict__ t_eid, int32_t* __restrict__ t_rel) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const int W = 2 * (k + 1) + 1, zero = k + 1;
+    for (int e = row_ptr[i]; e < row_ptr[i + 1]; ++e) {
+        int r = rel[e];
+        int order = r % W - zero;
+        int v = col[e];
+        int pos = t_ptr[v];
+        if (order > 0)
+            pos += i - min_l[v];
+        else if (order == 0)
+            pos += cnt_l[v];
+        else
+            pos += cnt_l[v] + (v < n ? 1 : 0) + (i - min_r[v]);
+        t_src[pos] = i;
+        t_eid[pos] = e;
+        t_rel[pos] = r;
+    }
+}
+
+__global__ void t_fill_spans(int n, int num_levels, int32_t e_tok, const int32_t* __restrict__ rel,
+                             const int32_t* __restrict__ t_ptr, const int32_t* __restrict__ cnt_l,
+                             const int32_t* __restrict__ cnt_r, int32_t* __restrict__ t_src,
+                             int32_t* __restrict__ t_eid, int32_t* __restrict__ t_rel) {
+    const int64_t a = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (a >= (int64_t)n * (num_levels - 1)) return;
+    int lev = 1 + (int)(a / n);
+    int t = (int)(a % n);
+    int32_t e = (int32_t)(e_tok + a);
+    int pos = t_ptr[t] + cnt_l[t] + 1 + cnt_r[t] + (lev - 1);  // after all token queries, by level
+    t_src[pos] = (int32_t)(level_offset(n, lev) + (t >> lev));
+    t_eid[pos] = e;
+    t_rel[pos] = rel[e];
+}
+
+// ---- host helpers -------------------------------------------------------------
+struct DeviceBuf {  // frees on scope exit unless released
+    void* p = nullptr;
+    ~DeviceBuf() {
+        if (p) (void)hipFree(p);
+    }
+    hipError_t alloc(size_t bytes) { return hipMalloc(&p, bytes ? bytes : 4); }
+    template <typename T>
+    T* as() const {
+        return static_cast<T*>(p);
+    }
+    void* release() {
+        void* r = p;
+        p = nullptr;
+        return r;
+    }
+};
+
+int exclusive_scan(const int32_t* in, int32_t* out, int m, int32_t total, int32_t* block_sums, hipStream_t st) {
+    int nblocks = (m + kScanBlock - 1) / kScanBlock;
+    if (nblocks > kScanBlock) return BPT_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(scan_blocks, dim3(nblocks), dim3(kScanThreads), 0, st, in, out, block_sums, m);
+    hipLaunchKernelGGL(scan_sums, dim3(1), dim3(kScanThreads), 0, st, block_sums, nblocks);
+    hipLaunchKernelGGL(scan_add, dim3((m + 1 + 255) / 256), dim3(256), 0, st, out, block_sums, m, total);
+    BPT_HIP(hipGetLastError());
+    return BPT_OK;
+}
+
+void free_schedule(Schedule& s) {
+    (void)hipFree(s.seg_row);
+    (void)hipFree(s.seg_begin);
+    (void)hipFree(s.seg_part);
+    (void)hipFree(s.tile_ptr);
+    (void)hipFree(s.multi_row);
+    (void)hipFree(s.multi_ptr);
+    s = Schedule();
+}
+
+template <typename T>
+int upload(const std::vector<T>& h, T** d) {
+    BPT_HIP(hipMalloc((void**)d, std::max<size_t>(h.size(), 1) * sizeof(T)));
+    if (!h.empty()) BPT_HIP(hipMemcpy(*d, h.data(), h.size() * sizeof(T), hipMemcpyHostToDevice));
+    return BPT_OK;
+}
+
+// Cut rows into segments of at most kSeg edges and group consecutive segments
+// into tiles of about kTileWork work units.  Rows without edges still get one
+// (empty) segment so that their outputs are written.
+int make_schedule(const std::vector<int32_t>& ptr, Schedule& out) {
+    const int32_t rows = (int32_t)ptr.size() - 1;
+    std::vector<int32_t> seg_row, seg_begin, seg_part, tile_ptr, multi_row, multi_ptr;
+    seg_row.reserve(rows + rows / 8);
+    seg_begin.reserve(rows + rows / 8);
+    seg_part.reserve(rows + rows / 8);
+    tile_ptr.push_back(0);
+    multi_ptr.push_back(0);
+    int64_t work = 0;
+    int32_t parts = 0;
+    for (int32_t u = 0; u < rows; ++u) {
+        const int32_t b = ptr[u], deg = ptr[u + 1] - b;
+        const int32_t nseg = deg <= kSeg ? 1 : (deg + kSeg - 1) / kSeg;
+        for (int32_t s = 0; s < nseg; ++s) {
+            const int32_t len = std::min<int32_t>(kSeg, deg - s * kSeg);
+            seg_row.push_back(u);
+            seg_begin.push_back(b + s * kSeg);
+            seg_part.push_back(nseg > 1 ? parts++ : -1);
+            work += std::max<int32_t>(len, 0) + kRowCost;
+            if (work >= kTileWork) {
+                tile_ptr.push_back((int32_t)seg_row.size());
+                work = 0;
+            }
+        }
+        if (nseg > 1) {
+            multi_row.push_back(u);
+            multi_ptr.push_back(parts);
+        }
+    }
+    if (tile_ptr.back() != (int32_t)seg_row.size()) tile_ptr.push_back((int32_t)seg_row.size());
+    out.num_segs = (int32_t)seg_row.size();
+    out.num_tiles = (int32_t)tile_ptr.size() - 1;
+    out.num_multi = (int32_t)multi_row.size();
+    out.num_part = parts;
+    int rc;
+    if ((rc = upload(seg_row, &out.seg_row)) || (rc = upload(seg_begin, &out.seg_begin)) ||
+        (rc = upload(seg_part, &out.seg_part)) || (rc = upload(tile_ptr, &out.tile_ptr)) ||
+        (rc = upload(multi_row, &out.multi_row)) || (rc = upload(multi_ptr, &out.multi_ptr)))
+        return rc;
+    return BPT_OK;
+}
+
+int build(int32_t n, int32_t k, int32_t causal, hipStream_t st, bpt_graph* g) {
+    const int num_levels = 32 - __builtin_clz((unsigned)n);  // log2(n) + 1
+    const int num_nodes = 2 * n - 1;
+    g->n = n;
+    g->k = k;
+    g->causal = causal ? 1 : 0;
+    g->num_nodes = num_nodes;
+    g->num_levels = num_levels;
+    g->rel_width = 2 * (k + 1) + 1;
+    BPT_HIP(hipGetDevice(&g->device));
+    hipDeviceProp_t prop;
+    BPT_HIP(hipGetDeviceProperties(&prop, g->device));
+    g->num_cus = prop.multiProcessorCount;
+
+    const int tb = kScanThreads;
+    const int token_blocks = (n + tb - 1) / tb;
+    const int node_blocks = (num_nodes + tb - 1) / tb;
+
+    DeviceBuf deg, counters, block_sums;
+    BPT_HIP(deg.alloc(sizeof(int32_t) * (size_t)num_nodes));
+    BPT_HIP(counters.alloc(16));
+    BPT_HIP(block_sums.alloc(sizeof(int32_t) * kScanBlock));
+    BPT_HIP(hipMemsetAsync(counters.p, 0, 16, st));
+    unsigned long long* d_total = counters.as<unsigned long long>();
+    int32_t* d_maxlev = counters.as<int32_t>() + 2;
+
+    // 1. token degrees, their total, and the deepest contextual level
+    hipLaunchKernelGGL(token_degree, dim3(token_blocks), dim3(tb), 0, st, n, k, g->causal, deg.as<int32_t>(), d_total,
+                       d_maxlev);
+    BPT_HIP(hipGetLastError());
+    struct {
+        unsigned long long total;
+        int32_t maxlev, pad;
+    } h = {0, 0, 0};
+    BPT_HIP(hipMemcpyAsync(&h, counters.p, 16, hipMemcpyDeviceToHost, st));
+    BPT_HIP(hipStreamSynchronize(st));
+    const int64_t e_tok = (int64_t)h.total;
+    const int64_t e_all = e_tok + (int64_t)n * (num_levels - 1);
+    if (e_all > INT32_MAX) return BPT_ERR_OVERFLOW;
+    g->num_edges = e_all;
+    g->ctx_levels = std::max(1, (int)h.maxlev);
+
+    // 2. row_ptr: scan of the token degrees; span rows are closed form (fill_spans)
+    BPT_HIP(hipMalloc((void**)&g->row_ptr, sizeof(int32_t) * ((size_t)num_nodes + 1)));
+    BPT_HIP(hipMalloc((void**)&g->col, sizeof(int32_t) * (size_t)e_all));
+    BPT_HIP(hipMalloc((void**)&g->rel, sizeof(int32_t) * (size_t)e_all));
+    int rc = exclusive_scan(deg.as<int32_t>(), g->row_ptr, n, (int32_t)e_tok, block_sums.as<int32_t>(), st);
+    if (rc) return rc;
+
+    // 3. fill
+    hipLaunchKernelGGL(fill_tokens, dim3(token_blocks), dim3(tb), 0, st, n, k, g->causal, g->row_ptr, g->col, g->rel);
+    const int64_t aff = (int64_t)n * (num_levels - 1);
+    const int aff_blocks = (int)((std::max<int64_t>(aff, n) + tb - 1) / tb);
+    hipLaunchKernelGGL(fill_spans, dim3(aff_blocks), dim3(tb), 0, st, n, k, num_levels, (int32_t)e_tok, g->row_ptr,
+                       g->col, g->rel);
+    BPT_HIP(hipGetLastError());
+
+    // 4. transposed adjacency
+    DeviceBuf cnt_l, cnt_r, min_l, min_r;
+    const size_t nb = sizeof(int32_t) * (size_t)num_nodes;
+    BPT_HIP(cnt_l.alloc(nb));
+    BPT_HIP(cnt_r.alloc(nb));
+    BPT_HIP(min_l.alloc(nb));
+    BPT_HIP(min_r.alloc(nb));
+    BPT_HIP(hipMalloc((void**)&g->t_ptr, sizeof(int32_t) * ((size_t)num_nodes + 1)));
+    BPT_HIP(hipMalloc((void**)&g->t_src, sizeof(int32_t) * (size_t)e_all));
+    BPT_HIP(hipMalloc((void**)&g->t_eid, sizeof(int32_t) * (size_t)e_all));
+    BPT_HIP(hipMalloc((void**)&g->t_rel, sizeof(int32_t) * (size_t)e_all));
+    hipLaunchKernelGGL(t_init, dim3(node_blocks), dim3(tb), 0, st, num_nodes, cnt_l.as<int32_t>(), cnt_r.as<int32_t>(),
+                       min_l.as<int32_t>(), min_r.as<int32_t>());
+    hipLaunchKernelGGL(t_count, dim3(token_blocks), dim3(tb), 0, st, n, k, g->row_ptr, g->col, g->rel,
+                       cnt_l.as<int32_t>(), cnt_r.as<int32_t>(), min_l.as<int32_t>(), min_r.as<int32_t>());
+    hipLaunchKernelGGL(t_degree, dim3(node_blocks), dim3(tb), 0, st, n, num_nodes, num_levels, cnt_l.as<int32_t>(),
+                       cnt_r.as<int32_t>(), deg.as<int32_t>());
+    BPT_HIP(hipGetLastError());
+    rc = exclusive_scan(deg.as<int32_t>(), g->t_ptr, num_nodes, (int32_t)e_all, block_sums.as<int32_t>(), st);
+    if (rc) return rc;
+    hipLaunchKernelGGL(t_fill_tokens, dim3(token_blocks), dim3(tb), 0, st, n, k, g->row_ptr, g->col, g->rel, g->t_ptr,
+                       cnt_l.as<int32_t>(), min_l.as<int32_t>(), min_r.as<int32_t>(), g->t_src, g->t_eid, g->t_rel);
+    if (aff > 0)
+        hipLaunchKernelGGL(t_fill_spans, dim3((int)((aff + tb - 1) / tb)), dim3(tb), 0, st, n, num_levels,
+                           (int32_t)e_tok, g->rel, g->t_ptr, cnt_l.as<int32_t>(), cnt_r.as<int32_t>(), g->t_src,
+                           g->t_eid, g->t_rel);
+    BPT_HIP(hipGetLastError());
+
+    // 5. launch schedules (host, from the two row-pointer arrays)
+    std::vector<int32_t> h_ptr((size_t)num_nodes + 1), h_tptr((size_t)num_nodes + 1);
+    BPT_HIP(hipMemcpyAsync(h_ptr.data(), g->row_ptr, sizeof(int32_t) * h_ptr.size(), hipMemcpyDeviceToHost, st));
+    BPT_HIP(hipMemcpyAsync(h_tptr.data(), g->t_ptr, sizeof(int32_t) * h_tptr.size(), hipMemcpyDeviceToHost, st));
+    BPT_HIP(hipStreamSynchronize(st));
+    if ((rc = make_schedule(h_ptr, g->fwd))) return rc;
+    if ((rc = make_schedule(h_tptr, g->tr))) return rc;
+    return BPT_OK;
+}
+
+}  // namespace
+}  // namespace bpt
+
+extern "C" {
+
+void bpt_graph_destroy(bpt_graph_t* g) {
+    if (!g) return;
+    (void)hipFree(g->row_ptr);
+    (void)hipFree(g->col);
+    (void)hipFree(g->rel);
+    (void)hipFree(g->t_ptr);
+    (void)hipFree(g->t_src);
+    (void)hipFree(g->t_eid);
+    (void)hipFree(g->t_rel);
+    bpt::free_schedule(g->fwd);
+    bpt::free_schedule(g->tr);
+    delete g;
+}
+
+int bpt_build_graph(int32_t n, int32_t k, int32_t causal, void* stream, bpt_graph_t** out) {
+    if (!out) return BPT_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (n < 2 || k < 1) return BPT_ERR_INVALID_ARG;
+    if ((n & (n - 1)) != 0 || n > (1 << 22) || k > (1 << 20)) return BPT_ERR_UNSUPPORTED;
+    bpt_graph* g = new (std::nothrow) bpt_graph();
+    if (!g) return BPT_ERR_ALLOC;
+    int rc;
+    try {
+        rc = bpt::build(n, k, causal, static_cast<hipStream_t>(stream), g);
+    } catch (const std::bad_alloc&) {
+        rc = BPT_ERR_ALLOC;
+    }
+    if (rc != BPT_OK) {
+        bpt_graph_destroy(g);
+        return rc;
+    }
+    *out = g;
+    return BPT_OK;
+}
+
+int bpt_graph_info(const bpt_graph_t* g, int32_t* n, int32_t* k, int32_t* causal, int32_t* num_nodes,
+                   int64_t* num_edges, int32_t* num_levels, int32_t* rel_width, int32_t* ctx_levels) {
+    if (!g) return BPT_ERR_INVALID_ARG;
+    if (n) *n = g->n;
+    if (k) *k = g->k;
+    if (causal) *causal = g->causal;
+    if (num_nodes) *num_nodes = g->num_nodes;
+    if (num_edges) *num_edges = g->num_edges;
+    if (num_levels) *num_levels = g->num_levels;
+    if (rel_width) *rel_width = g->rel_width;
+    if (ctx_levels) *ctx_levels = g->ctx_levels;
+    return BPT_OK;
+}
+
+int bpt_graph_csr(const bpt_graph_t* g, const int32_t** row_ptr, const int32_t** col, const int32_t** rel) {
+    if (!g) return BPT_ERR_INVALID_ARG;
+    if (row_ptr) *row_ptr = g->row_ptr;
+    if (col) *col = g->col;
+    if (rel) *rel = g->rel;
+    return BPT_OK;
+}
+
+int bpt_graph_transposed(const bpt_graph_t* g, const int32_t** t_ptr, const int32_t** t_src, const int32_t** t_eid) {
+    if (!g) return BPT_ERR_INVALID_ARG;
+    if (t_ptr) *t_ptr = g->t_ptr;
+    if (t_src) *t_src = g->t_src;
+    if (t_eid) *t_eid = g->t_eid;
+    return BPT_OK;
+}
+
+static int copy_out(int32_t* dst, const int32_t* src, size_t count) {
+    if (dst && count) BPT_HIP(hipMemcpy(dst, src, count * sizeof(int32_t), hipMemcpyDeviceToHost));
+    return BPT_OK;
+}
+
+int bpt_graph_to_host(const bpt_graph_t* g, int32_t* row_ptr, int32_t* col, int32_t* rel) {
+    if (!g) return BPT_ERR_INVALID_ARG;
+    int rc;
+    if ((rc = copy_out(row_ptr, g->row_ptr, (size_t)g->num_nodes + 1))) return rc;
+    if ((rc = copy_out(col, g->col, (size_t)g->num_edges))) return rc;
+    return copy_out(rel, g->rel, (size_t)g->num_edges);
+}
+
+int bpt_graph_transposed_to_host(const bpt_graph_t* g, int32_t* t_ptr, int32_t* t_src, int32_t* t_eid) {
+    if (!g) return BPT_ERR_INVALID_ARG;
+    int rc;
+    if ((rc = copy_out(t_ptr, g->t_ptr, (size_t)g->num_nodes + 1))) return rc;
+    if ((rc = copy_out(t_src, g->t_src, (size_t)g->num_edges))) return rc;
+    return copy_out(t_eid, g->t_eid, (size_t)g->num_edges);
+}
+
+const char* bpt_strerror(int status) {
+    switch (status) {
+        case BPT_OK: return "ok";
+        case BPT_ERR_INVALID_ARG: return "invalid argument";
+        case BPT_ERR_UNSUPPORTED: return "unsupported size, width or dtype";
+        case BPT_ERR_ALLOC: return "allocation failed";
+        case BPT_ERR_LAUNCH: return "HIP call or kernel launch failed";
+        case BPT_ERR_OVERFLOW: return "graph has more than INT32_MAX edges";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,53 @@
+// Internal definitions shared by the library's translation units (not installed).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "bpt.h"
+
+namespace bpt {
+
+constexpr int kD = 64;            // head width the kernels are written for
+constexpr int kSeg = 512;         // most edges one wavefront handles for one row
+constexpr int kTileWork = 4096;   // target work (edges + per-row cost) of one workgroup tile
+constexpr int kRowCost = 24;      // per-row overhead, in edge equivalents, for tile balancing
+constexpr int kPartStride = 66;   // forward partial: 64 accumulators, running max, running sum
+
+// A launch schedule over one adjacency (by query node, or transposed by key
+// node).  Rows are cut into segments of at most kSeg edges; a wavefront
+// processes one segment.  Rows with several segments write partial results that
+// a merge kernel combines.  Segments are grouped into tiles of about equal work.
+struct Schedule {
+    int32_t num_segs = 0, num_tiles = 0, num_multi = 0, num_part = 0;
+    int32_t* seg_row = nullptr;    // [num_segs]   row (node id) of the segment
+    int32_t* seg_begin = nullptr;  // [num_segs]   first edge of the segment
+    int32_t* seg_part = nullptr;   // [num_segs]   partial slot, or -1 if the row has one segment
+    int32_t* tile_ptr = nullptr;   // [num_tiles+1] segments of a tile
+    int32_t* multi_row = nullptr;  // [num_multi]  rows that have several segments
+    int32_t* multi_ptr = nullptr;  // [num_multi+1] their partial slots
+};
+
+}  // namespace bpt
+
+struct bpt_graph {
+    int32_t n = 0, k = 0, causal = 0;
+    int32_t num_nodes = 0, num_levels = 0, rel_width = 0, ctx_levels = 0;
+    int64_t num_edges = 0;
+    int device = 0;
+    int num_cus = 0;
+    // CSR by query node
+    int32_t *row_ptr = nullptr, *col = nullptr, *rel = nullptr;
+    // transposed adjacency by key node
+    int32_t *t_ptr = nullptr, *t_src = nullptr, *t_eid = nullptr, *t_rel = nullptr;
+    bpt::Schedule fwd, tr;
+};
+
+#define BPT_HIP(expr)                                  \
+    do {                                               \
+        hipError_t e__ = (expr);                       \
+        if (e__ != hipSuccess) {                       \
+            (void)hipGetLastError();                   \
+            return e__ == hipErrorOutOfMemory ? BPT_ERR_ALLOC : BPT_ERR_LAUNCH; \
+        }                                              \
+    } while (0)

@@ -1,0 +1,213 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle.
+
+Graph arrays must be bit-identical.  Attention must agree within max-abs 1e-4
+for fp32 tensors and 2e-2 for bf16 tensors with fp32 accumulation (the
+tolerances the benchmark spec fixes); where the outputs are much larger than 1 in
+magnitude (d_rel sums B*H*n terms) the bound is applied relative to the
+largest oracle value, as stated at `tol_for`.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1911_04070_amd import binding as bpt
+from paper_1911_04070_amd.workloads import WORKLOADS, Workload, make_inputs, shrink
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def tol_for(dtype, ref):
+    """max-abs tolerance; scaled by max|ref| once that exceeds 1 (sums of many terms)."""
+    return TOL[dtype] * max(1.0, float(np.abs(ref).max()))
+
+
+def to_dev(x, dtype):
+    t = torch.from_numpy(np.ascontiguousarray(x))
+    if dtype == "bf16":
+        t = t.to(torch.bfloat16)              # exact: values are already bf16-representable
+    return t.cuda()
+
+
+def host(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+GRAPHS = [(2, 1, False), (2, 1, True), (4, 1, False), (8, 3, True), (16, 2, False), (64, 64, False), (64, 100, True),
+          (512, 4, False), (1024, 1, False), (2048, 100, True), (8192, 8, True), (65536, 4, True)] + \
+         [(4096, k, False) for k in (2, 4, 8, 16, 32)]
+
+
+@pytest.mark.parametrize("n,k,causal", GRAPHS)
+def test_graph_is_bit_exact(n, k, causal):
+    say("graph", n, k, causal)
+    ref = oracle.build_graph(n, k, causal)
+    g = bpt.bpt_build_graph(n, k, causal)
+    assert (g.num_nodes, g.num_edges, g.num_levels, g.rel_width) == (ref.num_nodes, ref.num_edges, ref.num_levels,
+                                                                      ref.rel_width)
+    row_ptr, col, rel = g.csr_to_host()
+    assert np.array_equal(row_ptr, ref.row_ptr)
+    assert np.array_equal(col, ref.col)
+    assert np.array_equal(rel, ref.rel)
+    t_ptr, t_src, t_eid = g.transposed_to_host()
+    r_ptr, r_src, r_eid = oracle.transpose(ref)
+    assert np.array_equal(t_ptr, r_ptr)
+    assert np.array_equal(t_src, r_src)
+    assert np.array_equal(t_eid, r_eid)
+    # levels on which some token has contextual nodes
+    lv = ref.rel[:ref.row_ptr[n]] // ref.rel_width
+    assert g.ctx_levels == int(lv.max()) + 1
+    g.destroy()
+
+
+def test_graph_errors_on_device():
+    import ctypes
+    L = bpt.load_library()
+    h = ctypes.c_void_p()
+    # complete token graph at n = 65536 has n^2 > INT32_MAX edges
+    assert L.bpt_build_graph(65536, 65536, 0, None, ctypes.byref(h)) == bpt.BPT_ERR_OVERFLOW
+    assert h.value is None
+    with pytest.raises(bpt.BptError):
+        bpt.bpt_build_graph(48, 2, False)
+
+
+def run_case(w: Workload, x=None, layout="bhnd", check_bwd=None):
+    """Runs forward (+ backward) of a workload on the GPU and on the oracle and compares."""
+    say("case", w)
+    if x is None:
+        x = make_inputs(w)
+    ref_g = oracle.build_graph(w.n, w.k, w.causal)
+    g = bpt.bpt_build_graph(w.n, w.k, w.causal)
+    dev = {}
+    for key in ("Q", "K", "V", "dO"):
+        if key in x:
+            t = to_dev(x[key], w.dtype)
+            if layout == "bnhd":               # same logical tensor, node-major memory
+                t = t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+            dev[key] = t
+    rel_d = to_dev(x["Rel"], w.dtype)
+    out_d, lse_d = bpt.bpt_attn_fwd(g, dev["Q"], dev["K"], dev["V"], rel_d, scale=w.scale)
+    torch.cuda.synchronize()
+    out_r, lse_r, _ = oracle.attn_fwd(ref_g, x["Q"], x["K"], x["V"], x["Rel"], w.scale)
+    res = {}
+    for name, got, ref in (("out", host(out_d), out_r), ("lse", host(lse_d), lse_r)):
+        err = float(np.abs(got - ref).max())
+        res[name] = err
+        assert np.isfinite(got).all(), name
+        assert err <= tol_for(w.dtype, ref), (name, err)
+    do_bwd = w.backward if check_bwd is None else check_bwd
+    if do_bwd:
+        grads = bpt.bpt_attn_bwd(g, dev["Q"], dev["K"], dev["V"], rel_d, lse_d, dev["dO"], scale=w.scale)
+        torch.cuda.synchronize()
+        refs = oracle.attn_bwd(ref_g, x["Q"], x["K"], x["V"], x["Rel"], x["dO"], w.scale)
+        for name, got_t, ref in zip(("dQ", "dK", "dV", "d_rel"), grads, refs[:4]):
+            got = host(got_t)
+            err = float(np.abs(got - ref).max())
+            res[name] = err
+            res[name + "_max"] = float(np.abs(ref).max())
+            assert np.isfinite(got).all(), name
+            assert err <= tol_for(w.dtype, ref), (name, err, float(np.abs(ref).max()))
+        # r_anc never changes the output (it shifts a whole span row): its gradient is zero
+        anc = host(grads[3])[1:, w.k + 1]
+        assert np.abs(anc).max() <= TOL[w.dtype]
+    say("   max-abs errors", {k: float("%.3g" % v) for k, v in res.items()})
+    g.destroy()
+    return res
+
+
+def test_forward_tiny_fp32():
+    # configuration 1: n=512, k=4, bidirectional, one head of 64, fp32, forward only
+    run_case(WORKLOADS["tiny"])
+
+
+SMALL = [
+    ("f32", 2, 1, False, 1, 1), ("f32", 4, 1, True, 2, 1), ("f32", 8, 3, False, 1, 3), ("f32", 16, 2, False, 2, 2),
+    ("f32", 64, 100, False, 1, 2), ("f32", 256, 3, True, 2, 3), ("f32", 2048, 5, False, 1, 2),
+    ("bf16", 2, 1, True, 1, 1), ("bf16", 32, 2, False, 3, 2), ("bf16", 128, 200, True, 1, 2),
+    ("bf16", 1024, 7, False, 2, 2), ("bf16", 4096, 3, True, 1, 3),
+]
+
+
+@pytest.mark.parametrize("dtype,n,k,causal,B,H", SMALL)
+def test_forward_backward_small(dtype, n, k, causal, B, H):
+    w = Workload("small", 7, n, k, causal, B, H, 64, dtype, True)
+    run_case(w)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_strided_layout(dtype):
+    # [B,N,H,D] memory (all heads of a node adjacent) through the stride arguments
+    w = Workload("strided", 8, 512, 4, False, 2, 4, 64, dtype, True)
+    run_case(w, layout="bnhd")
+
+
+def test_rows_cut_into_several_segments():
+    # n=4096, k=40: token rows of > 512 edges, span rows up to 4096, key nodes with
+    # thousands of queries: every merge path runs
+    w = Workload("segments", 9, 4096, 40, False, 1, 2, 64, "bf16", True)
+    run_case(w)
+    w = Workload("segments32", 9, 2048, 12, True, 1, 1, 64, "f32", True)
+    run_case(w)
+
+
+FULL = ["cls", "lm", "xl", "ksweep2", "ksweep4", "ksweep8", "ksweep16", "ksweep32"]
+
+
+@pytest.mark.parametrize("name", FULL)
+def test_full_size_configuration(name):
+    # configurations 2-5 at their full sizes, every output element against the oracle
+    run_case(WORKLOADS[name])
+
+
+def test_scale_argument_and_default():
+    w = Workload("scale", 10, 256, 2, False, 1, 2, 64, "f32", True)
+    x = make_inputs(w)
+    ref_g = oracle.build_graph(w.n, w.k, w.causal)
+    g = bpt.bpt_build_graph(w.n, w.k, w.causal)
+    Q, K, V, R = (to_dev(x[k], "f32") for k in ("Q", "K", "V", "Rel"))
+    for scale, eff in ((None, 0.125), (0.05, 0.05)):
+        out_d, lse_d = bpt.bpt_attn_fwd(g, Q, K, V, R, scale=scale)
+        out_r, lse_r, _ = oracle.attn_fwd(ref_g, x["Q"], x["K"], x["V"], x["Rel"], eff)
+        assert np.abs(host(out_d) - out_r).max() <= 1e-4
+        assert np.abs(host(lse_d) - lse_r).max() <= 1e-4
+    g.destroy()
+
+
+def test_run_to_run_reproducibility():
+    w = shrink(WORKLOADS["lm"], B=1, H=2, n=2048)
+    x = make_inputs(w)
+    g = bpt.bpt_build_graph(w.n, w.k, w.causal)
+    Q, K, V, R, dO = (to_dev(x[k], "bf16") for k in ("Q", "K", "V", "Rel", "dO"))
+    runs = []
+    for _ in range(3):
+        out, lse = bpt.bpt_attn_fwd(g, Q, K, V, R, scale=w.scale)
+        grads = bpt.bpt_attn_bwd(g, Q, K, V, R, lse, dO, scale=w.scale)
+        torch.cuda.synchronize()
+        runs.append([t.clone() for t in (out, lse) + tuple(grads)])
+    for other in runs[1:]:
+        for name, a, b in zip(("out", "lse", "dQ", "dK", "dV"), runs[0], other):
+            assert torch.equal(a, b), name                      # no atomics on these paths
+        drift = float((runs[0][5] - other[5]).abs().max())
+        say("   d_rel run-to-run max diff", drift)              # LDS fp32 atomics: rounding order only
+        assert drift <= 1e-3
+    g.destroy()
+
+
+def test_invalid_arguments_on_device():
+    g = bpt.bpt_build_graph(64, 2, False)
+    Q = torch.zeros(1, 1, g.num_nodes, 64, device="cuda")
+    R = torch.zeros(g.num_levels, g.rel_width, 64, device="cuda")
+    with pytest.raises(ValueError):
+        bpt.bpt_attn_fwd(g, Q[:, :, :-1], Q[:, :, :-1], Q[:, :, :-1], R)
+    Q32 = torch.zeros(1, 1, g.num_nodes, 32, device="cuda")
+    R32 = torch.zeros(g.num_levels, g.rel_width, 32, device="cuda")
+    with pytest.raises(bpt.BptError) as e:
+        bpt.bpt_attn_fwd(g, Q32, Q32, Q32, R32)
+    assert e.value.status == bpt.BPT_ERR_UNSUPPORTED
+    g.destroy()
