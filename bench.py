@@ -110,10 +110,9 @@ def main():
                                                       workspace=ws_f), reps)}
     if w.backward:
         stage_ms["bwd_query_side"] = timed(
-            lambda: bpt.bpt_attn_bwd_query_side(g, Q, K, V, R, lse, dO, grads[0], ws_b, scale=w.scale), reps)
+            lambda: bpt.bpt_attn_bwd_query_side(g, Q, K, V, R, lse, dO, grads[0], grads[3], ws_b, scale=w.scale), reps)
         stage_ms["bwd_key_side"] = timed(
-            lambda: bpt.bpt_attn_bwd_key_side(g, Q, K, V, R, lse, dO, grads[1], grads[2], grads[3], ws_b,
-                                              scale=w.scale), reps)
+            lambda: bpt.bpt_attn_bwd_key_side(g, Q, K, V, R, lse, dO, grads[1], grads[2], ws_b, scale=w.scale), reps)
     per_edge = {"fwd": FWD_BYTES_PER_EDGE, "bwd_query_side": BWD_Q_BYTES_PER_EDGE,
                 "bwd_key_side": BWD_KV_BYTES_PER_EDGE}
     kernel_of = {"fwd": "fwd_kernel", "bwd_query_side": "bwd_q_kernel", "bwd_key_side": "bwd_kv_kernel"}
@@ -133,14 +132,17 @@ def main():
     if not args.no_cpu_baseline:
         import oracle
         og = oracle.build_graph(w.n, w.k, w.causal)
-        t0 = time.perf_counter()
-        _, _, used = oracle.attn_fwd(og, x["Q"], x["K"], x["V"], x["Rel"], w.scale)
-        if w.backward:
-            oracle.attn_bwd(og, x["Q"], x["K"], x["V"], x["Rel"], x["dO"], w.scale)
-        dt = time.perf_counter() - t0
-        cpu = {"value": round(edge_inst / dt, 1), "unit": "edges/s", "cores": used, "kind": "oracle",
-               "sample": "the whole workload once (forward%s), fp64, %.1f s" % (
-                   " + backward" if w.backward else "", dt)}
+        passes, dt, used = 0, 0.0, 1
+        while passes < 1 or (dt < 5.0 and passes < 50):      # a few seconds of wall time on all cores
+            t0 = time.perf_counter()
+            _, _, used = oracle.attn_fwd(og, x["Q"], x["K"], x["V"], x["Rel"], w.scale)
+            if w.backward:
+                oracle.attn_bwd(og, x["Q"], x["K"], x["V"], x["Rel"], x["dO"], w.scale)
+            dt += time.perf_counter() - t0
+            passes += 1
+        cpu = {"value": round(edge_inst * passes / dt, 1), "unit": "edges/s", "cores": used, "kind": "oracle",
+               "sample": "the whole workload, %d pass(es) of forward%s in fp64, %.1f s wall" % (
+                   passes, " + backward" if w.backward else "", dt)}
 
     res = {
         "metric": "BPT graph-attention fwd+bwd edges/sec" if w.backward else "BPT graph-attention fwd edges/sec",

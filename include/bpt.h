@@ -119,10 +119,10 @@ int bpt_attn_fwd(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q, cons
  *   d_rel[id] = scale * sum over batch, head and edges with id_e = id of dS_e q_u
  * lse is the forward's result; the forward's `out` is not needed (delta is
  * recomputed in fp32 from p and dP).  dQ, dK, dV (fp32, the tensor strides) and
- * d_rel (fp32, contiguous [num_levels][W][D]) are overwritten.  dQ, dK and dV are
- * run-to-run identical (dK, dV are reduced over the transposed adjacency, no
- * atomics); d_rel is accumulated with fp32 atomics in on-chip memory and is
- * reproducible only up to rounding order.  workspace: device scratch of at least
+ * d_rel (fp32, contiguous [num_levels][W][D]) are overwritten.  No atomics are
+ * used anywhere: dK and dV are reduced over the transposed adjacency and d_rel as
+ * a dense contraction over blocks of token rows, so all four gradients are
+ * run-to-run identical.  workspace: device scratch of at least
  * bpt_attn_bwd_workspace bytes. */
 int bpt_attn_bwd(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q, const void* K,
                  const void* V, const void* rel, const float* lse, const void* dout, float* dQ,
@@ -130,17 +130,17 @@ int bpt_attn_bwd(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q, cons
                  void* stream);
 
 /* The two stages of bpt_attn_bwd, callable on their own (same workspace, same
- * stream order): the query side walks the CSR rows and produces dQ and, in the
- * workspace, delta; the key side walks the transposed adjacency, reads that delta
- * and produces dK, dV and d_rel.  bpt_attn_bwd is exactly the first followed by
- * the second. */
+ * stream order): the query side walks the CSR rows and produces dQ, d_rel and,
+ * in the workspace, delta; the key side walks the transposed adjacency, reads that
+ * delta and produces dK and dV.  bpt_attn_bwd is exactly the first followed by the
+ * second. */
 int bpt_attn_bwd_query_side(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q,
                             const void* K, const void* V, const void* rel, const float* lse,
-                            const void* dout, float* dQ, void* workspace, size_t workspace_bytes,
-                            void* stream);
+                            const void* dout, float* dQ, float* d_rel, void* workspace,
+                            size_t workspace_bytes, void* stream);
 int bpt_attn_bwd_key_side(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q,
                           const void* K, const void* V, const void* rel, const float* lse,
-                          const void* dout, float* dK, float* dV, float* d_rel, void* workspace,
+                          const void* dout, float* dK, float* dV, void* workspace,
                           size_t workspace_bytes, void* stream);
 
 /* Static, never NULL. */

@@ -76,9 +76,9 @@ def load_library() -> ctypes.CDLL:
     L.bpt_attn_bwd.restype = ctypes.c_int
     L.bpt_attn_bwd.argtypes = [vp, P(BptShape)] + [vp] * 11 + [sz, vp]
     L.bpt_attn_bwd_query_side.restype = ctypes.c_int
-    L.bpt_attn_bwd_query_side.argtypes = [vp, P(BptShape)] + [vp] * 8 + [sz, vp]
+    L.bpt_attn_bwd_query_side.argtypes = [vp, P(BptShape)] + [vp] * 9 + [sz, vp]
     L.bpt_attn_bwd_key_side.restype = ctypes.c_int
-    L.bpt_attn_bwd_key_side.argtypes = [vp, P(BptShape)] + [vp] * 10 + [sz, vp]
+    L.bpt_attn_bwd_key_side.argtypes = [vp, P(BptShape)] + [vp] * 9 + [sz, vp]
     L.bpt_strerror.restype = ctypes.c_char_p
     L.bpt_strerror.argtypes = [ctypes.c_int]
     _lib = L
@@ -247,28 +247,28 @@ def bpt_attn_bwd(g: Graph, Q, K, V, rel, lse, dout, scale: Optional[float] = Non
     return dQ, dK, dV, d_rel
 
 
-def bpt_attn_bwd_query_side(g: Graph, Q, K, V, rel, lse, dout, dQ, workspace, scale: Optional[float] = None):
-    """First stage of the backward: dQ, and delta into the workspace."""
+def bpt_attn_bwd_query_side(g: Graph, Q, K, V, rel, lse, dout, dQ, d_rel, workspace,
+                            scale: Optional[float] = None):
+    """First stage of the backward: dQ, d_rel, and delta into the workspace."""
     L = load_library()
     shp = _shape_of(g, Q, scale)
     _check(L.bpt_attn_bwd_query_side(g.handle, ctypes.byref(shp), Q.data_ptr(), K.data_ptr(), V.data_ptr(),
                                      rel.data_ptr(), lse.data_ptr(), dout.data_ptr(), dQ.data_ptr(),
-                                     workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                     d_rel.data_ptr(), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                                      _stream_ptr()), "bpt_attn_bwd_query_side")
-    return dQ
+    return dQ, d_rel
 
 
-def bpt_attn_bwd_key_side(g: Graph, Q, K, V, rel, lse, dout, dK, dV, d_rel, workspace,
-                          scale: Optional[float] = None):
-    """Second stage of the backward: dK, dV, d_rel (reads delta from the workspace)."""
+def bpt_attn_bwd_key_side(g: Graph, Q, K, V, rel, lse, dout, dK, dV, workspace, scale: Optional[float] = None):
+    """Second stage of the backward: dK, dV (reads delta from the workspace)."""
     L = load_library()
     shp = _shape_of(g, Q, scale)
     _check(L.bpt_attn_bwd_key_side(g.handle, ctypes.byref(shp), Q.data_ptr(), K.data_ptr(), V.data_ptr(),
                                    rel.data_ptr(), lse.data_ptr(), dout.data_ptr(), dK.data_ptr(), dV.data_ptr(),
-                                   d_rel.data_ptr(), workspace.data_ptr(),
+                                   workspace.data_ptr(),
                                    workspace.numel() * workspace.element_size(), _stream_ptr()),
            "bpt_attn_bwd_key_side")
-    return dK, dV, d_rel
+    return dK, dV
 
 
 def workspace_bytes(g: Graph, like: torch.Tensor, scale: Optional[float] = None) -> Tuple[int, int]:

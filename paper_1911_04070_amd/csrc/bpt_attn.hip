@@ -7,9 +7,13 @@
 // edge: each lane holds 8 of the 64 features, so a 128-byte bf16 row is one 16-byte
 // load per lane and 8 edges are in flight per wavefront instruction.  Each 8-lane
 // group keeps its own online-softmax state; the 8 groups are merged once per
-// segment.  Workgroups are persistent: each walks a strided list of tiles inside
-// the share of its XCD, so workgroups that run together on one XCD touch
-// neighbouring rows and the K/V rows they share stay in that XCD's L2.
+// segment.  The edge loop is software pipelined: neighbour indices are fetched two
+// iterations ahead and the gathered rows one iteration ahead, so the dependent
+// index -> row latency overlaps the arithmetic of the current edges.
+//
+// Workgroups are persistent: each walks a strided list of tiles inside the share of
+// its XCD, so workgroups that run together on one XCD touch neighbouring rows and
+// the rows they share stay in that XCD's L2.
 //
 // The relative-position table is staged in LDS once per workgroup when it fits.
 // For span rows every edge carries the same r_anc(level), which only shifts all
@@ -26,9 +30,8 @@ typedef uint16_t bf16_t;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kNegBig = -1.0e30f;
-constexpr int kThreads = 512;            // 8 wavefronts per workgroup (forward, query-side backward)
+constexpr int kThreads = 512;            // 8 wavefronts per workgroup
 constexpr int kWaves = kThreads / 64;
-constexpr int kThreadsKV = 1024;         // 16 wavefronts share one LDS copy of d_rel (key-side backward)
 constexpr int kQPartStride = 132;        // query-side partial: A[64], Bv[64], delta, padding
 
 struct AttnArgs {
@@ -38,7 +41,10 @@ struct AttnArgs {
     float* lse_w;
     const float* lse_r;
     float *dQ, *dK, *dV, *d_rel;
-    float *delta, *part, *drel_part;
+    float2* stat;            // per (batch*head, node): (lse * log2(e), delta), written by the query side
+    float2* wp;              // per (batch*head, edge of a token row): (p_e dP_e, p_e), written by the query side
+    int64_t e_tok;           // edges of token rows (they come first in the CSR)
+    float *part, *drel_part;
     int64_t sb, sh, sn;
     int32_t BH, H, N, n_tokens;
     float scale;
@@ -48,7 +54,8 @@ struct AttnArgs {
     const int32_t *seg_row, *seg_begin, *seg_part, *tile_ptr;
     int32_t num_tiles, num_part;
     int32_t rel_rows_lds;   // rows of the r table staged in LDS (0: read it from global memory)
-    int32_t drel_rows_lds;  // rows of d_rel accumulated in LDS (0: global atomics)
+    int32_t drel_rows;      // rows of d_rel that token rows can touch (levels with contextual edges)
+    int32_t drel_block;     // token rows per block of rel_grad_kernel
     int32_t rel_rows;       // rows of the whole table
 };
 
@@ -67,34 +74,74 @@ __device__ __forceinline__ float sum8(float x) {
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
 
-__device__ __forceinline__ void load8(const float* p, float (&x)[8]) {
-    const float4 a = *reinterpret_cast<const float4*>(p);
-    const float4 b = *reinterpret_cast<const float4*>(p + 4);
-    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
-    x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+// all 8 groups (lanes with the same feature chunk) get the sum / max
+__device__ __forceinline__ float slots_sum(float x) {
+    x += __shfl_xor(x, 8);
+    x += __shfl_xor(x, 16);
+    x += __shfl_xor(x, 32);
+    return x;
 }
-__device__ __forceinline__ void load8(const bf16_t* p, float (&x)[8]) {
-    const uint4 w = *reinterpret_cast<const uint4*>(p);
-    x[0] = __uint_as_float(w.x << 16); x[1] = __uint_as_float(w.x & 0xFFFF0000u);
-    x[2] = __uint_as_float(w.y << 16); x[3] = __uint_as_float(w.y & 0xFFFF0000u);
-    x[4] = __uint_as_float(w.z << 16); x[5] = __uint_as_float(w.z & 0xFFFF0000u);
-    x[6] = __uint_as_float(w.w << 16); x[7] = __uint_as_float(w.w & 0xFFFF0000u);
+__device__ __forceinline__ float slots_max(float x) {
+    x = fmaxf(x, __shfl_xor(x, 8));
+    x = fmaxf(x, __shfl_xor(x, 16));
+    x = fmaxf(x, __shfl_xor(x, 32));
+    return x;
 }
-__device__ __forceinline__ void store8(float* p, const float (&x)[8]) {
-    *reinterpret_cast<float4*>(p) = make_float4(x[0], x[1], x[2], x[3]);
-    *reinterpret_cast<float4*>(p + 4) = make_float4(x[4], x[5], x[6], x[7]);
+// Sum x[0..7] over the 8 groups with 7 exchanges instead of 24: at every step a lane
+// keeps one half of its values and hands the other half to its partner.  Returns
+// the total of element slot_elem(lane) of the lane's feature chunk.
+__device__ __forceinline__ int slot_elem(int lane) {
+    return ((lane >> 5) & 1) * 4 + ((lane >> 4) & 1) * 2 + ((lane >> 3) & 1);
+}
+__device__ __forceinline__ float reduce_slots8(const float (&x)[8], int lane) {
+    const bool h32 = lane & 32, h16 = lane & 16, h8 = lane & 8;
+    float y[4], z[2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) y[i] = (h32 ? x[i + 4] : x[i]) + __shfl_xor(h32 ? x[i] : x[i + 4], 32);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) z[i] = (h16 ? y[i + 2] : y[i]) + __shfl_xor(h16 ? y[i] : y[i + 2], 16);
+    return (h8 ? z[1] : z[0]) + __shfl_xor(h8 ? z[0] : z[1], 8);
+}
+
+// ---- 8 consecutive features of one row, as loaded -----------------------------------
+template <typename T>
+struct Row;
+template <>
+struct Row<bf16_t> {
+    uint4 w;
+};
+template <>
+struct Row<float> {
+    float4 a, b;
+};
+__device__ __forceinline__ Row<bf16_t> load_row(const bf16_t* p) {
+    Row<bf16_t> r;
+    r.w = *reinterpret_cast<const uint4*>(p);
+    return r;
+}
+__device__ __forceinline__ Row<float> load_row(const float* p) {
+    Row<float> r;
+    r.a = *reinterpret_cast<const float4*>(p);
+    r.b = *reinterpret_cast<const float4*>(p + 4);
+    return r;
+}
+__device__ __forceinline__ void unpack(const Row<bf16_t>& r, float (&x)[8]) {
+    x[0] = __uint_as_float(r.w.x << 16); x[1] = __uint_as_float(r.w.x & 0xFFFF0000u);
+    x[2] = __uint_as_float(r.w.y << 16); x[3] = __uint_as_float(r.w.y & 0xFFFF0000u);
+    x[4] = __uint_as_float(r.w.z << 16); x[5] = __uint_as_float(r.w.z & 0xFFFF0000u);
+    x[6] = __uint_as_float(r.w.w << 16); x[7] = __uint_as_float(r.w.w & 0xFFFF0000u);
+}
+__device__ __forceinline__ void unpack(const Row<float>& r, float (&x)[8]) {
+    x[0] = r.a.x; x[1] = r.a.y; x[2] = r.a.z; x[3] = r.a.w;
+    x[4] = r.b.x; x[5] = r.b.y; x[6] = r.b.z; x[7] = r.b.w;
+}
+template <typename T>
+__device__ __forceinline__ void load8(const T* p, float (&x)[8]) {
+    unpack(load_row(p), x);
 }
 __device__ __forceinline__ uint32_t to_bf16_bits(float f) {  // round to nearest even
     uint32_t u = __float_as_uint(f);
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-}
-__device__ __forceinline__ void store8(bf16_t* p, const float (&x)[8]) {
-    uint4 w;
-    w.x = to_bf16_bits(x[0]) | (to_bf16_bits(x[1]) << 16);
-    w.y = to_bf16_bits(x[2]) | (to_bf16_bits(x[3]) << 16);
-    w.z = to_bf16_bits(x[4]) | (to_bf16_bits(x[5]) << 16);
-    w.w = to_bf16_bits(x[6]) | (to_bf16_bits(x[7]) << 16);
-    *reinterpret_cast<uint4*>(p) = w;
 }
 __device__ __forceinline__ void store1(float* p, float x) { *p = x; }
 __device__ __forceinline__ void store1(bf16_t* p, float x) { *p = (bf16_t)to_bf16_bits(x); }
@@ -122,6 +169,101 @@ struct TileWalk {
 };
 
 // ---- forward --------------------------------------------------------------------
+// One segment [e0, e1) of row u (e1 > e0).  SPAN: the row is a span node.
+template <typename T, bool REL_LDS, bool SPAN>
+__device__ __forceinline__ void fwd_segment(const AttnArgs& a, const T* rel_s, int bh, int64_t base, int u, int e0,
+                                            int e1, int part, int lane) {
+    const int slot = lane >> 3, sub = lane & 7;
+    const T* Kb = static_cast<const T*>(a.K) + base + sub * 8;
+    const T* Vb = static_cast<const T*>(a.V) + base + sub * 8;
+    const T* relg = static_cast<const T*>(a.rel) + sub * 8;
+    const int last = e1 - 1;
+
+    // indices two iterations ahead, rows one iteration ahead
+    int c0 = a.ia[min(e0 + slot, last)], c1 = a.ia[min(e0 + 8 + slot, last)];
+    int r0 = 0, r1 = 0;
+    if (!SPAN) {
+        r0 = a.ib[min(e0 + slot, last)];
+        r1 = a.ib[min(e0 + 8 + slot, last)];
+    }
+    Row<T> k0 = load_row(Kb + (int64_t)c0 * a.sn), v0 = load_row(Vb + (int64_t)c0 * a.sn);
+
+    float q[8];
+    load8(static_cast<const T*>(a.Q) + base + (int64_t)u * a.sn + sub * 8, q);
+    const float qscale = a.scale * kLog2e;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) q[i] *= qscale;
+    float shift = 0.f;
+    if (SPAN) {  // r_anc(level) is common to the whole row
+        float r[8], d = 0.f;
+        load8(relg + (int64_t)a.ib[e0] * kD, r);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) d += q[i] * r[i];
+        shift = sum8(d);
+    }
+    float m = kNegBig, l = 0.f, acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+
+    for (int eb = e0; eb < e1; eb += 8) {
+        const int c2 = a.ia[min(eb + 16 + slot, last)];
+        int r2 = 0;
+        if (!SPAN) r2 = a.ib[min(eb + 16 + slot, last)];
+        const Row<T> k1 = load_row(Kb + (int64_t)c1 * a.sn), v1 = load_row(Vb + (int64_t)c1 * a.sn);
+
+        const bool valid = eb + slot < e1;
+        float kk[8], vv[8], d = 0.f;
+        unpack(k0, kk);
+        if (!SPAN) {
+            float r[8];
+            if (REL_LDS)
+                load8(rel_s + r0 * kD + sub * 8, r);
+            else
+                load8(relg + (int64_t)r0 * kD, r);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) d += q[i] * (kk[i] + r[i]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) d += q[i] * kk[i];
+        }
+        float sc = sum8(d) + shift;
+        sc = valid ? sc : kNegBig;
+        const float mn = fmaxf(m, sc);
+        const float corr = fast_exp2(m - mn);
+        const float p = valid ? fast_exp2(sc - mn) : 0.f;
+        unpack(v0, vv);
+        l = l * corr + p;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = acc[i] * corr + p * vv[i];
+        m = mn;
+
+        k0 = k1;
+        v0 = v1;
+        c1 = c2;
+        r0 = r1;
+        r1 = r2;
+    }
+    // merge the 8 groups: common max, rescale, then sum
+    const float mall = slots_max(m);
+    const float c = fast_exp2(m - mall);
+    l = slots_sum(l * c);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] *= c;
+    const float mine = reduce_slots8(acc, lane);
+    const int col = sub * 8 + slot_elem(lane);
+    if (part < 0) {
+        store1(static_cast<T*>(a.out) + base + (int64_t)u * a.sn + col, l > 0.f ? mine / l : 0.f);
+        if (lane == 0) a.lse_w[(int64_t)bh * a.N + u] = (mall + fast_log2(l)) * kLn2;
+    } else {
+        float* dst = a.part + ((int64_t)bh * a.num_part + part) * kPartStride;
+        dst[col] = mine;
+        if (lane == 0) {
+            dst[64] = mall;
+            dst[65] = l;
+        }
+    }
+}
+
 template <typename T, bool REL_LDS>
 __global__ void __launch_bounds__(kThreads) fwd_kernel(const AttnArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -132,101 +274,21 @@ __global__ void __launch_bounds__(kThreads) fwd_kernel(const AttnArgs a) {
     }
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform: row bookkeeping stays scalar
-    const int slot = lane >> 3, sub = lane & 7;
-    const float qscale = a.scale * kLog2e;
-    const T* relg = static_cast<const T*>(a.rel);
-
+    const int nwaves = blockDim.x >> 6;
     for (TileWalk w(a.BH * a.num_tiles); w.t < w.t_end; w.t += w.step) {
         const int bh = w.t / a.num_tiles, tile = w.t - bh * a.num_tiles;
         const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
-        const T* Qb = static_cast<const T*>(a.Q) + base;
-        const T* Kb = static_cast<const T*>(a.K) + base;
-        const T* Vb = static_cast<const T*>(a.V) + base;
         const int s1 = a.tile_ptr[tile + 1];
-        for (int s = a.tile_ptr[tile] + wave; s < s1; s += kWaves) {
+        for (int s = a.tile_ptr[tile] + wave; s < s1; s += nwaves) {
             const int u = a.seg_row[s];
             const int e0 = a.seg_begin[s];
             const int e1 = min(e0 + kSeg, a.ptr[u + 1]);
             const int part = a.seg_part[s];
-            const bool span = u >= a.n_tokens;
-
-            float q[8];
-            load8(Qb + (int64_t)u * a.sn + sub * 8, q);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) q[i] *= qscale;
-            float shift = 0.f;
-            if (span && e1 > e0) {  // r_anc(level) is common to the whole row
-                float r[8];
-                load8(relg + (int64_t)a.ib[e0] * kD + sub * 8, r);
-                float d = 0.f;
-#pragma unroll
-                for (int i = 0; i < 8; ++i) d += q[i] * r[i];
-                shift = sum8(d);
-            }
-
-            float m = kNegBig, l = 0.f, acc[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) acc[i] = 0.f;
-
-            for (int eb = e0; eb < e1; eb += 8) {
-                const bool valid = eb + slot < e1;
-                const int e = valid ? eb + slot : e1 - 1;
-                const int c = a.ia[e];
-                float kk[8], vv[8];
-                load8(Kb + (int64_t)c * a.sn + sub * 8, kk);
-                load8(Vb + (int64_t)c * a.sn + sub * 8, vv);
-                float d = 0.f;
-                if (!span) {
-                    const int rid = a.ib[e];
-                    float r[8];
-                    if (REL_LDS)
-                        load8(rel_s + rid * kD + sub * 8, r);
-                    else
-                        load8(relg + (int64_t)rid * kD + sub * 8, r);
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) d += q[i] * (kk[i] + r[i]);
-                } else {
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) d += q[i] * kk[i];
-                }
-                float sc = sum8(d) + shift;
-                sc = valid ? sc : kNegBig;
-                const float mn = fmaxf(m, sc);
-                const float corr = fast_exp2(m - mn);
-                const float p = valid ? fast_exp2(sc - mn) : 0.f;
-                l = l * corr + p;
-#pragma unroll
-                for (int i = 0; i < 8; ++i) acc[i] = acc[i] * corr + p * vv[i];
-                m = mn;
-            }
-            // merge the 8 groups
-#pragma unroll
-            for (int mask = 8; mask < 64; mask <<= 1) {
-                const float mo = __shfl_xor(m, mask), lo = __shfl_xor(l, mask);
-                const float mn = fmaxf(m, mo);
-                const float c1 = fast_exp2(m - mn), c2 = fast_exp2(mo - mn);
-                l = l * c1 + lo * c2;
-#pragma unroll
-                for (int i = 0; i < 8; ++i) acc[i] = acc[i] * c1 + __shfl_xor(acc[i], mask) * c2;
-                m = mn;
-            }
-            if (part < 0) {
-                const float inv = l > 0.f ? 1.f / l : 0.f;
-                if (slot == 0) {
-                    float o[8];
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) o[i] = acc[i] * inv;
-                    store8(static_cast<T*>(a.out) + base + (int64_t)u * a.sn + sub * 8, o);
-                }
-                if (lane == 0) a.lse_w[(int64_t)bh * a.N + u] = (m + fast_log2(l)) * kLn2;
-            } else {
-                float* dst = a.part + ((int64_t)bh * a.num_part + part) * kPartStride;
-                if (slot == 0) store8(dst + sub * 8, acc);
-                if (lane == 0) {
-                    dst[64] = m;
-                    dst[65] = l;
-                }
-            }
+            if (e1 <= e0) continue;  // no row of this adjacency is empty
+            if (u >= a.n_tokens)
+                fwd_segment<T, REL_LDS, true>(a, rel_s, bh, base, u, e0, e1, part, lane);
+            else
+                fwd_segment<T, REL_LDS, false>(a, rel_s, bh, base, u, e0, e1, part, lane);
         }
     }
 }
@@ -261,6 +323,100 @@ __global__ void __launch_bounds__(256) fwd_merge_kernel(const AttnArgs a, const 
 //   A = sum_e w_e (k_e + r_e),  Bv = sum_e p_e (k_e + r_e),
 // so one pass over the row gives delta exactly (in fp32, not through the rounded
 // `out`) and dQ.  For a span row r_anc drops out of dQ because the dS of a row sum to 0.
+template <typename T, bool REL_LDS, bool SPAN>
+__device__ __forceinline__ void bwd_q_segment(const AttnArgs& a, const T* rel_s, int bh, int64_t base, int u, int e0,
+                                              int e1, int part, int lane) {
+    const int slot = lane >> 3, sub = lane & 7;
+    const T* Kb = static_cast<const T*>(a.K) + base + sub * 8;
+    const T* Vb = static_cast<const T*>(a.V) + base + sub * 8;
+    const T* relg = static_cast<const T*>(a.rel) + sub * 8;
+    const int last = e1 - 1;
+
+    int c0 = a.ia[min(e0 + slot, last)], c1 = a.ia[min(e0 + 8 + slot, last)];
+    int r0 = 0, r1 = 0;
+    if (!SPAN) {
+        r0 = a.ib[min(e0 + slot, last)];
+        r1 = a.ib[min(e0 + 8 + slot, last)];
+    }
+    Row<T> k0 = load_row(Kb + (int64_t)c0 * a.sn), v0 = load_row(Vb + (int64_t)c0 * a.sn);
+
+    float qs[8], g[8];
+    load8(static_cast<const T*>(a.Q) + base + (int64_t)u * a.sn + sub * 8, qs);
+    load8(static_cast<const T*>(a.dout) + base + (int64_t)u * a.sn + sub * 8, g);
+    const float qscale = a.scale * kLog2e;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) qs[i] *= qscale;
+    const float lse2 = a.lse_r[(int64_t)bh * a.N + u] * kLog2e;
+    float shift = 0.f;
+    if (SPAN) {
+        float r[8], d = 0.f;
+        load8(relg + (int64_t)a.ib[e0] * kD, r);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) d += qs[i] * r[i];
+        shift = sum8(d);
+    }
+    float A[8], Bv[8], dl = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) A[i] = Bv[i] = 0.f;
+
+    for (int eb = e0; eb < e1; eb += 8) {
+        const int c2 = a.ia[min(eb + 16 + slot, last)];
+        int r2 = 0;
+        if (!SPAN) r2 = a.ib[min(eb + 16 + slot, last)];
+        const Row<T> k1 = load_row(Kb + (int64_t)c1 * a.sn), v1 = load_row(Vb + (int64_t)c1 * a.sn);
+
+        const bool valid = eb + slot < e1;
+        float kk[8], vv[8];
+        unpack(k0, kk);
+        unpack(v0, vv);
+        if (!SPAN) {
+            float r[8];
+            if (REL_LDS)
+                load8(rel_s + r0 * kD + sub * 8, r);
+            else
+                load8(relg + (int64_t)r0 * kD, r);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) kk[i] += r[i];
+        }
+        float d = 0.f, dp = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            d += qs[i] * kk[i];
+            dp += g[i] * vv[i];
+        }
+        const float sc = sum8(d) + shift;
+        const float dP = sum8(dp);
+        const float p = valid ? fast_exp2(sc - lse2) : 0.f;
+        const float wgt = p * dP;
+        dl += wgt;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            A[i] += wgt * kk[i];
+            Bv[i] += p * kk[i];
+        }
+        // what d_rel needs of this edge (dS_e = w_e - delta_u p_e once delta_u is known)
+        if (!SPAN && valid && sub == 0) a.wp[(int64_t)bh * a.e_tok + eb + slot] = make_float2(wgt, p);
+        k0 = k1;
+        v0 = v1;
+        c1 = c2;
+        r0 = r1;
+        r1 = r2;
+    }
+    dl = slots_sum(dl);
+    const int col = sub * 8 + slot_elem(lane);
+    if (part < 0) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) A[i] -= dl * Bv[i];
+        a.dQ[base + (int64_t)u * a.sn + col] = a.scale * reduce_slots8(A, lane);
+        if (lane == 0) a.stat[(int64_t)bh * a.N + u] = make_float2(lse2, dl);
+    } else {
+        float* dst = a.part + ((int64_t)bh * a.num_part + part) * kQPartStride;
+        dst[col] = reduce_slots8(A, lane);
+        dst[kD + col] = reduce_slots8(Bv, lane);
+        if (lane == 0) dst[2 * kD] = dl;
+    }
+}
+
 template <typename T, bool REL_LDS>
 __global__ void __launch_bounds__(kThreads) bwd_q_kernel(const AttnArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -271,101 +427,21 @@ __global__ void __launch_bounds__(kThreads) bwd_q_kernel(const AttnArgs a) {
     }
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int slot = lane >> 3, sub = lane & 7;
-    const float qscale = a.scale * kLog2e;
-    const T* relg = static_cast<const T*>(a.rel);
-
+    const int nwaves = blockDim.x >> 6;
     for (TileWalk w(a.BH * a.num_tiles); w.t < w.t_end; w.t += w.step) {
         const int bh = w.t / a.num_tiles, tile = w.t - bh * a.num_tiles;
         const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
-        const T* Qb = static_cast<const T*>(a.Q) + base;
-        const T* Kb = static_cast<const T*>(a.K) + base;
-        const T* Vb = static_cast<const T*>(a.V) + base;
-        const T* Gb = static_cast<const T*>(a.dout) + base;
         const int s1 = a.tile_ptr[tile + 1];
-        for (int s = a.tile_ptr[tile] + wave; s < s1; s += kWaves) {
+        for (int s = a.tile_ptr[tile] + wave; s < s1; s += nwaves) {
             const int u = a.seg_row[s];
             const int e0 = a.seg_begin[s];
             const int e1 = min(e0 + kSeg, a.ptr[u + 1]);
             const int part = a.seg_part[s];
-            const bool span = u >= a.n_tokens;
-
-            float qs[8], g[8];
-            load8(Qb + (int64_t)u * a.sn + sub * 8, qs);
-            load8(Gb + (int64_t)u * a.sn + sub * 8, g);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) qs[i] *= qscale;
-            const float lse2 = a.lse_r[(int64_t)bh * a.N + u] * kLog2e;
-            float shift = 0.f;
-            if (span && e1 > e0) {
-                float r[8], d = 0.f;
-                load8(relg + (int64_t)a.ib[e0] * kD + sub * 8, r);
-#pragma unroll
-                for (int i = 0; i < 8; ++i) d += qs[i] * r[i];
-                shift = sum8(d);
-            }
-            float A[8], Bv[8], dl = 0.f;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) A[i] = Bv[i] = 0.f;
-
-            for (int eb = e0; eb < e1; eb += 8) {
-                const bool valid = eb + slot < e1;
-                const int e = valid ? eb + slot : e1 - 1;
-                const int c = a.ia[e];
-                float kk[8], vv[8];
-                load8(Kb + (int64_t)c * a.sn + sub * 8, kk);
-                load8(Vb + (int64_t)c * a.sn + sub * 8, vv);
-                if (!span) {
-                    const int rid = a.ib[e];
-                    float r[8];
-                    if (REL_LDS)
-                        load8(rel_s + rid * kD + sub * 8, r);
-                    else
-                        load8(relg + (int64_t)rid * kD + sub * 8, r);
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) kk[i] += r[i];
-                }
-                float d = 0.f, dp = 0.f;
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    d += qs[i] * kk[i];
-                    dp += g[i] * vv[i];
-                }
-                const float sc = sum8(d) + shift;
-                const float dP = sum8(dp);
-                const float p = valid ? fast_exp2(sc - lse2) : 0.f;
-                const float wgt = p * dP;
-                dl += wgt;
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    A[i] += wgt * kk[i];
-                    Bv[i] += p * kk[i];
-                }
-            }
-#pragma unroll
-            for (int mask = 8; mask < 64; mask <<= 1) {
-                dl += __shfl_xor(dl, mask);
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    A[i] += __shfl_xor(A[i], mask);
-                    Bv[i] += __shfl_xor(Bv[i], mask);
-                }
-            }
-            if (part < 0) {
-                if (slot == 0) {
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) A[i] = a.scale * (A[i] - dl * Bv[i]);
-                    store8(a.dQ + base + (int64_t)u * a.sn + sub * 8, A);
-                }
-                if (lane == 0) a.delta[(int64_t)bh * a.N + u] = dl;
-            } else {
-                float* dst = a.part + ((int64_t)bh * a.num_part + part) * kQPartStride;
-                if (slot == 0) {
-                    store8(dst + sub * 8, A);
-                    store8(dst + kD + sub * 8, Bv);
-                }
-                if (lane == 0) dst[2 * kD] = dl;
-            }
+            if (e1 <= e0) continue;
+            if (u >= a.n_tokens)
+                bwd_q_segment<T, REL_LDS, true>(a, rel_s, bh, base, u, e0, e1, part, lane);
+            else
+                bwd_q_segment<T, REL_LDS, false>(a, rel_s, bh, base, u, e0, e1, part, lane);
         }
     }
 }
@@ -387,131 +463,187 @@ __global__ void __launch_bounds__(256) bwd_q_merge_kernel(const AttnArgs a, cons
     }
     const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
     a.dQ[base + (int64_t)u * a.sn + lane] = a.scale * (sa - dl * sb);
-    if (lane == 0) a.delta[(int64_t)bh * a.N + u] = dl;
+    if (lane == 0) a.stat[(int64_t)bh * a.N + u] = make_float2(a.lse_r[(int64_t)bh * a.N + u] * kLog2e, dl);
 }
 
-// ---- backward, key side: dK, dV and d_rel over the transposed adjacency ---------------
-// One wavefront per (segment of a) key node v; its queries u are gathered.  d_rel is
-// accumulated here because q_u and the exact dS_e are both at hand: each 8-lane group
-// sums the contributions of consecutive edges that share a relative-position id in
-// registers (for a coarse span the id changes only every 2^level queries) and adds
-// the run to the workgroup's LDS copy of d_rel with ds_add_f32; the copies are
-// summed by drel_reduce_kernel.  Edges whose query is a span carry r_anc, whose
-// gradient is zero, and are skipped.
-template <typename T, bool REL_LDS, bool DREL_LDS>
-__device__ __forceinline__ void flush_run(const AttnArgs& a, float* drel_s, int id, int sub, float (&dr)[8]) {
-    float* dst = (DREL_LDS ? drel_s : a.d_rel) + (int64_t)id * kD + sub * 8;
+// ---- backward, key side: dK, dV over the transposed adjacency -------------------------
+// One wavefront per (segment of a) key node v; the rows q_u, dout_u and the pair
+// (lse_u, delta_u) of its queries u are gathered.  No atomics: every key row is
+// reduced by one wavefront (or by the merge kernel, in segment order).
+template <typename T, bool REL_LDS>
+__device__ __forceinline__ void bwd_kv_segment(const AttnArgs& a, const T* rel_s, int bh, int64_t base, int v, int e0,
+                                               int e1, int part, int lane) {
+    const int slot = lane >> 3, sub = lane & 7;
+    const T* Qb = static_cast<const T*>(a.Q) + base + sub * 8;
+    const T* Gb = static_cast<const T*>(a.dout) + base + sub * 8;
+    const T* relg = static_cast<const T*>(a.rel) + sub * 8;
+    const float2* stat_b = a.stat + (int64_t)bh * a.N;
+    const float qscale = a.scale * kLog2e;
+
+    float dk[8], dv[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) atomicAdd(dst + i, dr[i] * a.scale);
+    for (int i = 0; i < 8; ++i) dk[i] = dv[i] = 0.f;
+
+    if (e1 > e0) {
+        const int last = e1 - 1;
+        int u0 = a.ia[min(e0 + slot, last)], u1 = a.ia[min(e0 + 8 + slot, last)];
+        int r0 = a.ib[min(e0 + slot, last)], r1 = a.ib[min(e0 + 8 + slot, last)];
+        Row<T> q0 = load_row(Qb + (int64_t)u0 * a.sn), g0 = load_row(Gb + (int64_t)u0 * a.sn);
+        float2 st0 = stat_b[u0];
+        float kk[8], vv[8];
+        load8(static_cast<const T*>(a.K) + base + (int64_t)v * a.sn + sub * 8, kk);
+        load8(static_cast<const T*>(a.V) + base + (int64_t)v * a.sn + sub * 8, vv);
+
+        for (int eb = e0; eb < e1; eb += 8) {
+            const int u2 = a.ia[min(eb + 16 + slot, last)];
+            const int r2 = a.ib[min(eb + 16 + slot, last)];
+            const Row<T> q1 = load_row(Qb + (int64_t)u1 * a.sn), g1 = load_row(Gb + (int64_t)u1 * a.sn);
+            const float2 st1 = stat_b[u1];
+
+            const bool valid = eb + slot < e1;
+            float q[8], g[8], r[8];
+            unpack(q0, q);
+            unpack(g0, g);
+            if (REL_LDS)
+                load8(rel_s + r0 * kD + sub * 8, r);
+            else
+                load8(relg + (int64_t)r0 * kD, r);
+            float d = 0.f, dp = 0.f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                d += q[i] * (kk[i] + r[i]);
+                dp += g[i] * vv[i];
+            }
+            const float sc = sum8(d) * qscale;
+            const float dP = sum8(dp);
+            const float p = valid ? fast_exp2(sc - st0.x) : 0.f;
+            const float dS = p * (dP - st0.y);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                dk[i] += dS * q[i];
+                dv[i] += p * g[i];
+            }
+            q0 = q1;
+            g0 = g1;
+            st0 = st1;
+            u1 = u2;
+            r0 = r1;
+            r1 = r2;
+        }
+    }
+    const float tk = reduce_slots8(dk, lane), tv = reduce_slots8(dv, lane);
+    const int col = sub * 8 + slot_elem(lane);
+    if (part < 0) {
+        a.dK[base + (int64_t)v * a.sn + col] = tk * a.scale;
+        a.dV[base + (int64_t)v * a.sn + col] = tv;
+    } else {
+        float* dst = a.part + ((int64_t)bh * a.num_part + part) * (2 * kD);
+        dst[col] = tk * a.scale;
+        dst[kD + col] = tv;
+    }
 }
 
-template <typename T, bool REL_LDS, bool DREL_LDS>
-__global__ void __launch_bounds__(kThreadsKV) bwd_kv_kernel(const AttnArgs a) {
+template <typename T, bool REL_LDS>
+__global__ void __launch_bounds__(kThreads) bwd_kv_kernel(const AttnArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     T* rel_s = reinterpret_cast<T*>(smem);
-    float* drel_s = reinterpret_cast<float*>(smem + (REL_LDS ? (size_t)a.rel_rows_lds * kD * sizeof(T) : 0));
-    if (REL_LDS) stage_table(rel_s, static_cast<const T*>(a.rel), a.rel_rows_lds * kD);
-    if (DREL_LDS)
-        for (int i = threadIdx.x; i < a.drel_rows_lds * kD; i += blockDim.x) drel_s[i] = 0.f;
-    if (REL_LDS || DREL_LDS) __syncthreads();
-
+    if (REL_LDS) {
+        stage_table(rel_s, static_cast<const T*>(a.rel), a.rel_rows_lds * kD);
+        __syncthreads();
+    }
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nwaves = blockDim.x >> 6;
-    const int slot = lane >> 3, sub = lane & 7;
-    const float qscale = a.scale * kLog2e;
-    const T* relg = static_cast<const T*>(a.rel);
-
     for (TileWalk w(a.BH * a.num_tiles); w.t < w.t_end; w.t += w.step) {
         const int bh = w.t / a.num_tiles, tile = w.t - bh * a.num_tiles;
         const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
-        const T* Qb = static_cast<const T*>(a.Q) + base;
-        const T* Kb = static_cast<const T*>(a.K) + base;
-        const T* Vb = static_cast<const T*>(a.V) + base;
-        const T* Gb = static_cast<const T*>(a.dout) + base;
-        const float* lse_b = a.lse_r + (int64_t)bh * a.N;
-        const float* delta_b = a.delta + (int64_t)bh * a.N;
         const int s1 = a.tile_ptr[tile + 1];
         for (int s = a.tile_ptr[tile] + wave; s < s1; s += nwaves) {
             const int v = a.seg_row[s];
             const int e0 = a.seg_begin[s];
             const int e1 = min(e0 + kSeg, a.ptr[v + 1]);
-            const int part = a.seg_part[s];
+            bwd_kv_segment<T, REL_LDS>(a, rel_s, bh, base, v, e0, e1, a.seg_part[s], lane);
+        }
+    }
+}
 
-            float kk[8], vv[8], dk[8], dv[8], dr[8];
-            load8(Kb + (int64_t)v * a.sn + sub * 8, kk);
-            load8(Vb + (int64_t)v * a.sn + sub * 8, vv);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) dk[i] = dv[i] = dr[i] = 0.f;
-            int cur = -1;
+// ---- backward: gradient of the relative-position table ---------------------------------
+// d_rel[id] = scale * sum over (batch, head, token row u, edge e of u with id_e = id) of
+// dS_e q_u.  Within a token row every edge has a different id, so for a block of R
+// consecutive token rows this is the dense contraction  d_rel += DS^T Q  with
+// DS[r][id] = dS of row r's edge with that id (0 if it has none) and Q the block's
+// query rows.  A workgroup builds DS (from the (w,p) pairs the query side stored and
+// delta) and Q in LDS, then every thread accumulates IPW outputs in registers:
+// wavefront g owns ids [g*IPW, (g+1)*IPW) of the workgroup's chunk of 8*IPW ids,
+// lane = feature.  Blocks are assigned statically and summed in a fixed
+// order, so d_rel is run-to-run identical.  blockIdx.y selects the chunk of ids.
+template <typename T, int IPW>
+__global__ void __launch_bounds__(kThreads) rel_grad_kernel(const AttnArgs a) {
+    constexpr int kDrelIdsPerWave = IPW, kDrelChunk = IPW * kWaves;
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int R = a.drel_block;
+    float* ds_s = reinterpret_cast<float*>(smem);           // [R][kDrelChunk]
+    float* q_s = ds_s + (size_t)R * kDrelChunk;             // [R][kD]
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int id0 = blockIdx.y * kDrelChunk;                // first id of this workgroup's chunk
+    const int blocks_per_bh = a.n_tokens / R;
+    const int total = a.BH * blocks_per_bh;
 
-            for (int eb = e0; eb < e1; eb += 8) {
-                const bool valid = eb + slot < e1;
-                const int e = valid ? eb + slot : e1 - 1;
-                const int u = a.ia[e];
-                const int rid = a.ib[e];
-                float q[8], g[8], r[8];
-                load8(Qb + (int64_t)u * a.sn + sub * 8, q);
-                load8(Gb + (int64_t)u * a.sn + sub * 8, g);
-                const float lse2 = lse_b[u] * kLog2e;
-                const float delta = delta_b[u];
-                if (REL_LDS)
-                    load8(rel_s + rid * kD + sub * 8, r);
-                else
-                    load8(relg + (int64_t)rid * kD + sub * 8, r);
-                float d = 0.f, dp = 0.f;
+    float acc[kDrelIdsPerWave];
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    d += q[i] * (kk[i] + r[i]);
-                    dp += g[i] * vv[i];
-                }
-                const float sc = sum8(d) * qscale;
-                const float dP = sum8(dp);
-                const float p = valid ? fast_exp2(sc - lse2) : 0.f;
-                const float dS = p * (dP - delta);
+    for (int i = 0; i < kDrelIdsPerWave; ++i) acc[i] = 0.f;
+
+    for (int blk = blockIdx.x; blk < total; blk += gridDim.x) {
+        const int bh = blk / blocks_per_bh, row0 = (blk - bh * blocks_per_bh) * R;
+        const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
+        for (int i = threadIdx.x; i < R * kDrelChunk; i += blockDim.x) ds_s[i] = 0.f;
+        {   // Q rows of the block: 8 lanes per row
+            const T* Qb = static_cast<const T*>(a.Q) + base;
+            for (int i = threadIdx.x; i < R * 8; i += blockDim.x) {
+                const int r = i >> 3, c = (i & 7) * 8;
+                float x[8];
+                load8(Qb + (int64_t)(row0 + r) * a.sn + c, x);
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    dk[i] += dS * q[i];
-                    dv[i] += p * g[i];
-                }
-                if (valid && u < a.n_tokens) {
-                    if (rid != cur) {
-                        if (cur >= 0) flush_run<T, REL_LDS, DREL_LDS>(a, drel_s, cur, sub, dr);
-                        cur = rid;
-#pragma unroll
-                        for (int i = 0; i < 8; ++i) dr[i] = 0.f;
-                    }
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) dr[i] += dS * q[i];
-                }
+                for (int j = 0; j < 8; ++j) q_s[r * kD + c + j] = x[j];
             }
-            if (cur >= 0) flush_run<T, REL_LDS, DREL_LDS>(a, drel_s, cur, sub, dr);
-#pragma unroll
-            for (int mask = 8; mask < 64; mask <<= 1) {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    dk[i] += __shfl_xor(dk[i], mask);
-                    dv[i] += __shfl_xor(dv[i], mask);
-                }
-            }
-            if (slot == 0) {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) dk[i] *= a.scale;
-                if (part < 0) {
-                    store8(a.dK + base + (int64_t)v * a.sn + sub * 8, dk);
-                    store8(a.dV + base + (int64_t)v * a.sn + sub * 8, dv);
-                } else {
-                    float* dst = a.part + ((int64_t)bh * a.num_part + part) * (2 * kD);
-                    store8(dst + sub * 8, dk);
-                    store8(dst + kD + sub * 8, dv);
+        }
+        __syncthreads();
+        // scatter dS of every edge of the block's rows: one wavefront per row, lanes over edges
+        const float2* wp_b = a.wp + (int64_t)bh * a.e_tok;
+        for (int r = wave; r < R; r += kWaves) {
+            const int u = row0 + r;
+            const float delta = a.stat[(int64_t)bh * a.N + u].y;
+            const int e1 = a.ptr[u + 1];
+            for (int e = a.ptr[u] + lane; e < e1; e += 64) {
+                const int id = a.ib[e] - id0;
+                if (id >= 0 && id < kDrelChunk) {
+                    const float2 x = wp_b[e];
+                    ds_s[r * kDrelChunk + id] = x.x - delta * x.y;
                 }
             }
         }
-    }
-    if (DREL_LDS) {
         __syncthreads();
-        float* dst = a.drel_part + (int64_t)blockIdx.x * a.drel_rows_lds * kD;
-        for (int i = threadIdx.x; i < a.drel_rows_lds * kD; i += blockDim.x) dst[i] = drel_s[i];
+        const float* dsw = ds_s + wave * kDrelIdsPerWave;
+        for (int r = 0; r < R; ++r) {
+            const float qv = q_s[r * kD + lane];
+#pragma unroll
+            for (int i = 0; i < kDrelIdsPerWave; i += 4) {
+                const float4 d4 = *reinterpret_cast<const float4*>(dsw + r * kDrelChunk + i);  // same address in all lanes
+                acc[i] += d4.x * qv;
+                acc[i + 1] += d4.y * qv;
+                acc[i + 2] += d4.z * qv;
+                acc[i + 3] += d4.w * qv;
+            }
+        }
+        __syncthreads();
+    }
+    // this workgroup's copy: [gridDim.x][drel_rows][kD]
+    float* dst = a.drel_part + (int64_t)blockIdx.x * a.drel_rows * kD;
+#pragma unroll
+    for (int i = 0; i < kDrelIdsPerWave; ++i) {
+        const int id = id0 + wave * kDrelIdsPerWave + i;
+        if (id < a.drel_rows) dst[id * kD + lane] = acc[i] * a.scale;
     }
 }
 
@@ -542,11 +674,6 @@ __global__ void drel_reduce_kernel(const float* __restrict__ parts, int num_part
     if (i < lds_elems)
         for (int p = 0; p < num_parts; ++p) acc += parts[(int64_t)p * lds_elems + i];
     d_rel[i] = acc;
-}
-
-__global__ void fill_zero_kernel(float* __restrict__ p, int count) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < count) p[i] = 0.f;
 }
 
 // ---- host side --------------------------------------------------------------------
@@ -580,7 +707,6 @@ int check_shape(const bpt_graph* g, const bpt_shape_t* s) {
 }
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
-inline size_t elem_size(const bpt_shape_t* s) { return s->dtype == BPT_BF16 ? 2 : 4; }
 
 // Resident workgroups per CU for a persistent launch, from the runtime's occupancy
 // calculator; the grid is that times the CU count, rounded down to a multiple of 8
@@ -654,50 +780,59 @@ int run_fwd(const bpt_graph* g, AttnArgs& a, hipStream_t st) {
     return BPT_OK;
 }
 
-// Workspace layout and LDS use of the backward.
+// Workspace layout of the backward and the launch shape of rel_grad_kernel.
 struct BwdPlan {
-    int rel_rows_kv = 0, drel_rows_kv = 0;  // LDS rows of the key-side kernel (0: global memory)
-    size_t lds_kv = 0;
-    int grid_kv = 8;
-    size_t off_delta = 0, off_qpart = 0, off_kvpart = 0, off_drel = 0, total = 0;
+    int drel_rows = 0;        // d_rel rows token rows can touch
+    int drel_ipw = 32;        // ids per wavefront: 8, 16 or 32
+    int drel_block = 32;      // token rows per block
+    int drel_grid_x = 8, drel_grid_y = 1;
+    size_t drel_lds = 0;
+    size_t off_stat = 0, off_wp = 0, off_qpart = 0, off_kvpart = 0, off_drel = 0, total = 0;
 };
 
 int plan_bwd(const bpt_graph* g, const bpt_shape_t* s, BwdPlan* p) {
     DeviceLimits lim;
     int rc = device_limits(g, &lim);
     if (rc) return rc;
-    const size_t es = elem_size(s);
-    const int ctx_rows = g->ctx_levels * g->rel_width;
-    const int all_rows = g->num_levels * g->rel_width;
-    const size_t rel_b = (size_t)all_rows * kD * es, drel_b = (size_t)ctx_rows * kD * sizeof(float);
-    if (rel_b + drel_b <= lim.lds) {
-        p->rel_rows_kv = all_rows;
-        p->drel_rows_kv = ctx_rows;
-        p->lds_kv = rel_b + drel_b;
-    } else if (drel_b <= lim.lds) {
-        p->drel_rows_kv = ctx_rows;
-        p->lds_kv = drel_b;
-    } else if (rel_b <= lim.lds) {
-        p->rel_rows_kv = all_rows;
-        p->lds_kv = rel_b;
-    }
-    p->grid_kv = std::max(8, lim.cus / 8 * 8);  // one 16-wavefront workgroup per CU
+    p->drel_rows = g->ctx_levels * g->rel_width;
+    p->drel_ipw = p->drel_rows <= 64 ? 8 : p->drel_rows <= 128 ? 16 : 32;
+    const int chunk = p->drel_ipw * kWaves;
+    p->drel_block = std::min(g->n, chunk > 128 ? 32 : 64);
+    p->drel_lds = (size_t)p->drel_block * (chunk + kD) * sizeof(float);
+    p->drel_grid_y = (p->drel_rows + chunk - 1) / chunk;
+    const int per_cu = (int)std::max<size_t>(1, std::min<size_t>(4, lim.lds / p->drel_lds));
+    const int64_t blocks = (int64_t)s->B * s->H * (g->n / p->drel_block);
+    p->drel_grid_x = (int)std::max<int64_t>(1, std::min<int64_t>(blocks, (int64_t)lim.cus * per_cu / p->drel_grid_y));
     const size_t bh = (size_t)s->B * s->H;
     size_t off = 0;
-    p->off_delta = off;
-    off += align_up(bh * g->num_nodes * sizeof(float));
+    p->off_stat = off;
+    off += align_up(bh * g->num_nodes * sizeof(float2));
+    p->off_wp = off;
+    off += align_up(bh * (size_t)g->num_token_edges * sizeof(float2));
     p->off_qpart = off;
     off += align_up(bh * g->fwd.num_part * kQPartStride * sizeof(float));
     p->off_kvpart = off;
     off += align_up(bh * g->tr.num_part * 2 * kD * sizeof(float));
     p->off_drel = off;
-    off += align_up((size_t)p->grid_kv * p->drel_rows_kv * kD * sizeof(float));
+    off += align_up((size_t)p->drel_grid_x * p->drel_rows * kD * sizeof(float));
     p->total = off;
     return BPT_OK;
 }
 
+template <typename T, int IPW>
+int launch_rel_grad(const BwdPlan& p, hipStream_t st, const AttnArgs& a) {
+    if (p.drel_lds > 65536)
+        BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rel_grad_kernel<T, IPW>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.drel_lds));
+    hipLaunchKernelGGL((rel_grad_kernel<T, IPW>), dim3(p.drel_grid_x, p.drel_grid_y), dim3(kThreads), p.drel_lds, st,
+                       a);
+    BPT_HIP(hipGetLastError());
+    return BPT_OK;
+}
+
+// query side: delta, dQ, then d_rel
 template <typename T>
-int run_bwd_q(const bpt_graph* g, AttnArgs& a, hipStream_t st) {
+int run_bwd_q(const bpt_graph* g, const BwdPlan& p, AttnArgs& a, hipStream_t st) {
     DeviceLimits lim;
     int rc = device_limits(g, &lim);
     if (rc) return rc;
@@ -709,6 +844,8 @@ int run_bwd_q(const bpt_graph* g, AttnArgs& a, hipStream_t st) {
     const size_t rel_b = (size_t)ctx_rows * kD * sizeof(T);
     const bool rel_lds = rel_b <= lim.lds;
     a.rel_rows_lds = rel_lds ? ctx_rows : 0;
+    a.drel_rows = p.drel_rows;
+    a.drel_block = p.drel_block;
     int grid = 8;
     if (rel_lds) {
         if ((rc = persistent_grid(bwd_q_kernel<T, true>, kThreads, rel_b, lim, &grid))) return rc;
@@ -724,45 +861,38 @@ int run_bwd_q(const bpt_graph* g, AttnArgs& a, hipStream_t st) {
                            g->fwd.multi_ptr, g->fwd.num_multi);
         BPT_HIP(hipGetLastError());
     }
+    rc = p.drel_ipw == 8 ? launch_rel_grad<T, 8>(p, st, a)
+                         : p.drel_ipw == 16 ? launch_rel_grad<T, 16>(p, st, a) : launch_rel_grad<T, 32>(p, st, a);
+    if (rc) return rc;
+    const int rel_elems = a.rel_rows * kD;
+    hipLaunchKernelGGL(drel_reduce_kernel, dim3((rel_elems + 255) / 256), dim3(256), 0, st, a.drel_part, p.drel_grid_x,
+                       p.drel_rows * kD, a.d_rel, rel_elems);
+    BPT_HIP(hipGetLastError());
     return BPT_OK;
 }
 
-template <typename T, bool REL_LDS, bool DREL_LDS>
-int launch_kv(const BwdPlan& p, hipStream_t st, const AttnArgs& a) {
-    if (p.lds_kv > 65536)
-        BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_kv_kernel<T, REL_LDS, DREL_LDS>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds_kv));
-    return launch(bwd_kv_kernel<T, REL_LDS, DREL_LDS>, p.grid_kv, kThreadsKV, p.lds_kv, st, a);
-}
-
 template <typename T>
-int run_bwd_kv(const bpt_graph* g, const BwdPlan& p, AttnArgs& a, hipStream_t st) {
+int run_bwd_kv(const bpt_graph* g, AttnArgs& a, hipStream_t st) {
+    DeviceLimits lim;
+    int rc = device_limits(g, &lim);
+    if (rc) return rc;
     a.ptr = g->t_ptr;
     a.ia = g->t_src;
     a.ib = g->t_rel;
     use_schedule(a, g->tr);
-    a.rel_rows_lds = p.rel_rows_kv;
-    a.drel_rows_lds = p.drel_rows_kv;
-    const int rel_elems = a.rel_rows * kD;
-    int rc;
-    if (p.drel_rows_kv == 0) {  // global atomics accumulate into d_rel itself
-        hipLaunchKernelGGL(fill_zero_kernel, dim3((rel_elems + 255) / 256), dim3(256), 0, st, a.d_rel, rel_elems);
-        BPT_HIP(hipGetLastError());
+    const int all_rows = g->num_levels * g->rel_width;  // queries that are spans carry r_anc of any level
+    const size_t rel_b = (size_t)all_rows * kD * sizeof(T);
+    const bool rel_lds = rel_b <= lim.lds;
+    a.rel_rows_lds = rel_lds ? all_rows : 0;
+    int grid = 8;
+    if (rel_lds) {
+        if ((rc = persistent_grid(bwd_kv_kernel<T, true>, kThreads, rel_b, lim, &grid))) return rc;
+        rc = launch(bwd_kv_kernel<T, true>, grid, kThreads, rel_b, st, a);
+    } else {
+        if ((rc = persistent_grid(bwd_kv_kernel<T, false>, kThreads, 0, lim, &grid))) return rc;
+        rc = launch(bwd_kv_kernel<T, false>, grid, kThreads, 0, st, a);
     }
-    if (p.rel_rows_kv && p.drel_rows_kv)
-        rc = launch_kv<T, true, true>(p, st, a);
-    else if (p.drel_rows_kv)
-        rc = launch_kv<T, false, true>(p, st, a);
-    else if (p.rel_rows_kv)
-        rc = launch_kv<T, true, false>(p, st, a);
-    else
-        rc = launch_kv<T, false, false>(p, st, a);
     if (rc) return rc;
-    if (p.drel_rows_kv) {
-        hipLaunchKernelGGL(drel_reduce_kernel, dim3((rel_elems + 255) / 256), dim3(256), 0, st, a.drel_part, p.grid_kv,
-                           p.drel_rows_kv * kD, a.d_rel, rel_elems);
-        BPT_HIP(hipGetLastError());
-    }
     if (g->tr.num_multi > 0) {
         const int items = a.BH * g->tr.num_multi;
         hipLaunchKernelGGL(bwd_kv_merge_kernel, dim3((items + 3) / 4), dim3(256), 0, st, a, g->tr.multi_row,
@@ -780,8 +910,8 @@ int backward(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q, const vo
     int rc = check_shape(g, s);
     if (rc) return rc;
     if (!Q || !K || !V || !rel || !lse || !dout) return BPT_ERR_INVALID_ARG;
-    if ((stages & kStageQ) && !dQ) return BPT_ERR_INVALID_ARG;
-    if ((stages & kStageKV) && (!dK || !dV || !d_rel)) return BPT_ERR_INVALID_ARG;
+    if ((stages & kStageQ) && (!dQ || !d_rel)) return BPT_ERR_INVALID_ARG;
+    if ((stages & kStageKV) && (!dK || !dV)) return BPT_ERR_INVALID_ARG;
     if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(rel) || misaligned(dout) || misaligned(dQ) ||
         misaligned(dK) || misaligned(dV) || misaligned(d_rel) || misaligned(workspace))
         return BPT_ERR_INVALID_ARG;
@@ -801,17 +931,19 @@ int backward(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q, const vo
     a.dK = dK;
     a.dV = dV;
     a.d_rel = d_rel;
-    a.delta = reinterpret_cast<float*>(ws + p.off_delta);
+    a.stat = reinterpret_cast<float2*>(ws + p.off_stat);
+    a.wp = reinterpret_cast<float2*>(ws + p.off_wp);
+    a.e_tok = g->num_token_edges;
     a.drel_part = reinterpret_cast<float*>(ws + p.off_drel);
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool bf = s->dtype == BPT_BF16;
     if (stages & kStageQ) {
         a.part = reinterpret_cast<float*>(ws + p.off_qpart);
-        if ((rc = bf ? run_bwd_q<bf16_t>(g, a, st) : run_bwd_q<float>(g, a, st))) return rc;
+        if ((rc = bf ? run_bwd_q<bf16_t>(g, p, a, st) : run_bwd_q<float>(g, p, a, st))) return rc;
     }
     if (stages & kStageKV) {
         a.part = reinterpret_cast<float*>(ws + p.off_kvpart);
-        if ((rc = bf ? run_bwd_kv<bf16_t>(g, p, a, st) : run_bwd_kv<float>(g, p, a, st))) return rc;
+        if ((rc = bf ? run_bwd_kv<bf16_t>(g, a, st) : run_bwd_kv<float>(g, a, st))) return rc;
     }
     return BPT_OK;
 }
@@ -868,16 +1000,16 @@ int bpt_attn_bwd(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q, cons
 }
 
 int bpt_attn_bwd_query_side(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q, const void* K, const void* V,
-                            const void* rel, const float* lse, const void* dout, float* dQ, void* workspace,
-                            size_t workspace_bytes, void* stream) {
-    return bpt::backward(g, s, Q, K, V, rel, lse, dout, dQ, nullptr, nullptr, nullptr, workspace, workspace_bytes,
+                            const void* rel, const float* lse, const void* dout, float* dQ, float* d_rel,
+                            void* workspace, size_t workspace_bytes, void* stream) {
+    return bpt::backward(g, s, Q, K, V, rel, lse, dout, dQ, nullptr, nullptr, d_rel, workspace, workspace_bytes,
                          stream, bpt::kStageQ);
 }
 
 int bpt_attn_bwd_key_side(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q, const void* K, const void* V,
-                          const void* rel, const float* lse, const void* dout, float* dK, float* dV, float* d_rel,
-                          void* workspace, size_t workspace_bytes, void* stream) {
-    return bpt::backward(g, s, Q, K, V, rel, lse, dout, nullptr, dK, dV, d_rel, workspace, workspace_bytes, stream,
+                          const void* rel, const float* lse, const void* dout, float* dK, float* dV, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+    return bpt::backward(g, s, Q, K, V, rel, lse, dout, nullptr, dK, dV, nullptr, workspace, workspace_bytes, stream,
                          bpt::kStageKV);
 }
 

@@ -449,6 +449,7 @@ int build(int32_t n, int32_t k, int32_t causal, hipStream_t st, bpt_graph* g) {
     const int64_t e_all = e_tok + (int64_t)n * (num_levels - 1);
     if (e_all > INT32_MAX) return BPT_ERR_OVERFLOW;
     g->num_edges = e_all;
+    g->num_token_edges = e_tok;
     g->ctx_levels = std::max(1, (int)h.maxlev);
 
     // 2. row_ptr: scan of the token degrees; span rows are closed form (fill_spans)

@@ -34,6 +34,7 @@ struct bpt_graph {
     int32_t n = 0, k = 0, causal = 0;
     int32_t num_nodes = 0, num_levels = 0, rel_width = 0, ctx_levels = 0;
     int64_t num_edges = 0;
+    int64_t num_token_edges = 0;  // edges of token rows: they come first in the CSR
     int device = 0;
     int num_cus = 0;
     // CSR by query node

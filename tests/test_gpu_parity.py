@@ -2,9 +2,7 @@
 
 Graph arrays must be bit-identical.  Attention must agree within max-abs 1e-4
 for fp32 tensors and 2e-2 for bf16 tensors with fp32 accumulation (the
-tolerances the benchmark spec fixes); where the outputs are much larger than 1 in
-magnitude (d_rel sums B*H*n terms) the bound is applied relative to the
-largest oracle value, as stated at `tol_for`.
+tolerances the benchmark spec fixes), as absolute bounds on every output.
 """
 import numpy as np
 import pytest
@@ -24,8 +22,8 @@ def say(*a):
 
 
 def tol_for(dtype, ref):
-    """max-abs tolerance; scaled by max|ref| once that exceeds 1 (sums of many terms)."""
-    return TOL[dtype] * max(1.0, float(np.abs(ref).max()))
+    """max-abs tolerance of the benchmark spec: 1e-4 for fp32 tensors, 2e-2 for bf16 tensors."""
+    return TOL[dtype]
 
 
 def to_dev(x, dtype):
@@ -191,11 +189,8 @@ def test_run_to_run_reproducibility():
         torch.cuda.synchronize()
         runs.append([t.clone() for t in (out, lse) + tuple(grads)])
     for other in runs[1:]:
-        for name, a, b in zip(("out", "lse", "dQ", "dK", "dV"), runs[0], other):
-            assert torch.equal(a, b), name                      # no atomics on these paths
-        drift = float((runs[0][5] - other[5]).abs().max())
-        say("   d_rel run-to-run max diff", drift)              # LDS fp32 atomics: rounding order only
-        assert drift <= 1e-3
+        for name, a, b in zip(("out", "lse", "dQ", "dK", "dV", "d_rel"), runs[0], other):
+            assert torch.equal(a, b), name                      # no atomics anywhere: bit-identical
     g.destroy()
 
 
