@@ -139,6 +139,23 @@ template <typename T>
 __device__ __forceinline__ void load8(const T* p, float (&x)[8]) {
     unpack(load_row(p), x);
 }
+// c + dot product of two 8-feature chunks, fp32 accumulation.  bf16 rows stay packed:
+// v_dot2c_f32_bf16 multiplies two pairs per instruction, so neither row is unpacked.
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+__device__ __forceinline__ float dot2_bf16(uint32_t x, uint32_t y, float c) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, x), __builtin_bit_cast(bf16x2_t, y), c, false);
+}
+__device__ __forceinline__ float dot8(const Row<bf16_t>& x, const Row<bf16_t>& y, float c) {
+    c = dot2_bf16(x.w.x, y.w.x, c);
+    c = dot2_bf16(x.w.y, y.w.y, c);
+    c = dot2_bf16(x.w.z, y.w.z, c);
+    return dot2_bf16(x.w.w, y.w.w, c);
+}
+__device__ __forceinline__ float dot8(const Row<float>& x, const Row<float>& y, float c) {
+    c += x.a.x * y.a.x; c += x.a.y * y.a.y; c += x.a.z * y.a.z; c += x.a.w * y.a.w;
+    c += x.b.x * y.b.x; c += x.b.y * y.b.y; c += x.b.z * y.b.z; c += x.b.w * y.b.w;
+    return c;
+}
 __device__ __forceinline__ uint32_t to_bf16_bits(float f) {  // round to nearest even
     uint32_t u = __float_as_uint(f);
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
@@ -188,19 +205,11 @@ __device__ __forceinline__ void fwd_segment(const AttnArgs& a, const T* rel_s, i
     }
     Row<T> k0 = load_row(Kb + (int64_t)c0 * a.sn), v0 = load_row(Vb + (int64_t)c0 * a.sn);
 
-    float q[8];
-    load8(static_cast<const T*>(a.Q) + base + (int64_t)u * a.sn + sub * 8, q);
+    const Row<T> q = load_row(static_cast<const T*>(a.Q) + base + (int64_t)u * a.sn + sub * 8);
     const float qscale = a.scale * kLog2e;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) q[i] *= qscale;
     float shift = 0.f;
-    if (SPAN) {  // r_anc(level) is common to the whole row
-        float r[8], d = 0.f;
-        load8(relg + (int64_t)a.ib[e0] * kD, r);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) d += q[i] * r[i];
-        shift = sum8(d);
-    }
+    if (SPAN)  // r_anc(level) is common to the whole row
+        shift = sum8(dot8(q, load_row(relg + (int64_t)a.ib[e0] * kD), 0.f)) * qscale;
     float m = kNegBig, l = 0.f, acc[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] = 0.f;
@@ -212,21 +221,10 @@ __device__ __forceinline__ void fwd_segment(const AttnArgs& a, const T* rel_s, i
         const Row<T> k1 = load_row(Kb + (int64_t)c1 * a.sn), v1 = load_row(Vb + (int64_t)c1 * a.sn);
 
         const bool valid = eb + slot < e1;
-        float kk[8], vv[8], d = 0.f;
-        unpack(k0, kk);
-        if (!SPAN) {
-            float r[8];
-            if (REL_LDS)
-                load8(rel_s + r0 * kD + sub * 8, r);
-            else
-                load8(relg + (int64_t)r0 * kD, r);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) d += q[i] * (kk[i] + r[i]);
-        } else {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) d += q[i] * kk[i];
-        }
-        float sc = sum8(d) + shift;
+        float vv[8], d = 0.f;
+        if (!SPAN) d = dot8(q, REL_LDS ? load_row(rel_s + r0 * kD + sub * 8) : load_row(relg + (int64_t)r0 * kD), 0.f);
+        d = dot8(q, k0, d);
+        float sc = sum8(d) * qscale + shift;
         sc = valid ? sc : kNegBig;
         const float mn = fmaxf(m, sc);
         const float corr = fast_exp2(m - mn);
@@ -340,9 +338,9 @@ __device__ __forceinline__ void bwd_q_segment(const AttnArgs& a, const T* rel_s,
     }
     Row<T> k0 = load_row(Kb + (int64_t)c0 * a.sn), v0 = load_row(Vb + (int64_t)c0 * a.sn);
 
-    float qs[8], g[8];
+    float qs[8];
     load8(static_cast<const T*>(a.Q) + base + (int64_t)u * a.sn + sub * 8, qs);
-    load8(static_cast<const T*>(a.dout) + base + (int64_t)u * a.sn + sub * 8, g);
+    const Row<T> g = load_row(static_cast<const T*>(a.dout) + base + (int64_t)u * a.sn + sub * 8);
     const float qscale = a.scale * kLog2e;
 #pragma unroll
     for (int i = 0; i < 8; ++i) qs[i] *= qscale;
@@ -366,9 +364,8 @@ __device__ __forceinline__ void bwd_q_segment(const AttnArgs& a, const T* rel_s,
         const Row<T> k1 = load_row(Kb + (int64_t)c1 * a.sn), v1 = load_row(Vb + (int64_t)c1 * a.sn);
 
         const bool valid = eb + slot < e1;
-        float kk[8], vv[8];
+        float kk[8];
         unpack(k0, kk);
-        unpack(v0, vv);
         if (!SPAN) {
             float r[8];
             if (REL_LDS)
@@ -378,14 +375,11 @@ __device__ __forceinline__ void bwd_q_segment(const AttnArgs& a, const T* rel_s,
 #pragma unroll
             for (int i = 0; i < 8; ++i) kk[i] += r[i];
         }
-        float d = 0.f, dp = 0.f;
+        float d = 0.f;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            d += qs[i] * kk[i];
-            dp += g[i] * vv[i];
-        }
+        for (int i = 0; i < 8; ++i) d += qs[i] * kk[i];
         const float sc = sum8(d) + shift;
-        const float dP = sum8(dp);
+        const float dP = sum8(dot8(g, v0, 0.f));
         const float p = valid ? fast_exp2(sc - lse2) : 0.f;
         const float wgt = p * dP;
         dl += wgt;
@@ -490,9 +484,8 @@ __device__ __forceinline__ void bwd_kv_segment(const AttnArgs& a, const T* rel_s
         int r0 = a.ib[min(e0 + slot, last)], r1 = a.ib[min(e0 + 8 + slot, last)];
         Row<T> q0 = load_row(Qb + (int64_t)u0 * a.sn), g0 = load_row(Gb + (int64_t)u0 * a.sn);
         float2 st0 = stat_b[u0];
-        float kk[8], vv[8];
-        load8(static_cast<const T*>(a.K) + base + (int64_t)v * a.sn + sub * 8, kk);
-        load8(static_cast<const T*>(a.V) + base + (int64_t)v * a.sn + sub * 8, vv);
+        const Row<T> kk = load_row(static_cast<const T*>(a.K) + base + (int64_t)v * a.sn + sub * 8);
+        const Row<T> vv = load_row(static_cast<const T*>(a.V) + base + (int64_t)v * a.sn + sub * 8);
 
         for (int eb = e0; eb < e1; eb += 8) {
             const int u2 = a.ia[min(eb + 16 + slot, last)];
@@ -501,21 +494,13 @@ __device__ __forceinline__ void bwd_kv_segment(const AttnArgs& a, const T* rel_s
             const float2 st1 = stat_b[u1];
 
             const bool valid = eb + slot < e1;
-            float q[8], g[8], r[8];
+            float q[8], g[8];
+            float d = dot8(q0, REL_LDS ? load_row(rel_s + r0 * kD + sub * 8) : load_row(relg + (int64_t)r0 * kD), 0.f);
+            d = dot8(q0, kk, d);
+            const float sc = sum8(d) * qscale;
+            const float dP = sum8(dot8(g0, vv, 0.f));
             unpack(q0, q);
             unpack(g0, g);
-            if (REL_LDS)
-                load8(rel_s + r0 * kD + sub * 8, r);
-            else
-                load8(relg + (int64_t)r0 * kD, r);
-            float d = 0.f, dp = 0.f;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                d += q[i] * (kk[i] + r[i]);
-                dp += g[i] * vv[i];
-            }
-            const float sc = sum8(d) * qscale;
-            const float dP = sum8(dp);
             const float p = valid ? fast_exp2(sc - st0.x) : 0.f;
             const float dS = p * (dP - st0.y);
 #pragma unroll
@@ -665,15 +650,22 @@ __global__ void __launch_bounds__(256) bwd_kv_merge_kernel(const AttnArgs a, con
     a.dV[at] = sv;
 }
 
-// d_rel = sum of the workgroups' LDS copies (rows the copies do not cover are zero)
-__global__ void drel_reduce_kernel(const float* __restrict__ parts, int num_parts, int lds_elems,
-                                   float* __restrict__ d_rel, int total_elems) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= total_elems) return;
+// d_rel = sum of the workgroups' copies, in a fixed order; rows the copies do not
+// cover are zero.  One workgroup per row of 64 features: 4 wavefronts each sum a
+// quarter of the copies (lane = feature, coalesced 256-byte reads), then combine.
+__global__ void __launch_bounds__(256) drel_reduce_kernel(const float* __restrict__ parts, int num_parts,
+                                                          int covered_rows, float* __restrict__ d_rel) {
+    __shared__ float s[4][kD];
+    const int row = blockIdx.x, lane = threadIdx.x & 63, grp = threadIdx.x >> 6;
     float acc = 0.f;
-    if (i < lds_elems)
-        for (int p = 0; p < num_parts; ++p) acc += parts[(int64_t)p * lds_elems + i];
-    d_rel[i] = acc;
+    if (row < covered_rows) {
+        const float* src = parts + (int64_t)row * kD + lane;
+        const int64_t stride = (int64_t)covered_rows * kD;
+        for (int p = grp; p < num_parts; p += 4) acc += src[p * stride];
+    }
+    s[grp][lane] = acc;
+    __syncthreads();
+    if (grp == 0) d_rel[row * kD + lane] = (s[0][lane] + s[1][lane]) + (s[2][lane] + s[3][lane]);
 }
 
 // ---- host side --------------------------------------------------------------------
@@ -864,9 +856,8 @@ int run_bwd_q(const bpt_graph* g, const BwdPlan& p, AttnArgs& a, hipStream_t st)
     rc = p.drel_ipw == 8 ? launch_rel_grad<T, 8>(p, st, a)
                          : p.drel_ipw == 16 ? launch_rel_grad<T, 16>(p, st, a) : launch_rel_grad<T, 32>(p, st, a);
     if (rc) return rc;
-    const int rel_elems = a.rel_rows * kD;
-    hipLaunchKernelGGL(drel_reduce_kernel, dim3((rel_elems + 255) / 256), dim3(256), 0, st, a.drel_part, p.drel_grid_x,
-                       p.drel_rows * kD, a.d_rel, rel_elems);
+    hipLaunchKernelGGL(drel_reduce_kernel, dim3(a.rel_rows), dim3(256), 0, st, a.drel_part, p.drel_grid_x,
+                       p.drel_rows, a.d_rel);
     BPT_HIP(hipGetLastError());
     return BPT_OK;
 }
