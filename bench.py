@@ -35,6 +35,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="lm")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy-mib", type=int, default=0,
+                    help="only run a plain device-to-device copy of this many MiB (10 times) and exit: the known "
+                         "traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
     return ap.parse_args()
 
 
@@ -47,6 +50,16 @@ def main():
 
     import numpy as np
     import torch
+
+    if args.calibrate_copy_mib > 0:
+        torch.cuda.set_device(0)
+        src = torch.ones(args.calibrate_copy_mib << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_mib": args.calibrate_copy_mib, "copies": 10}), flush=True)
+        return
 
     from paper_1911_04070_amd import binding as bpt
     from paper_1911_04070_amd.workloads import WORKLOADS, make_inputs
