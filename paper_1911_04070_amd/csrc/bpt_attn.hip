@@ -46,6 +46,9 @@ struct AttnArgs {
     int64_t e_tok;           // edges of token rows (they come first in the CSR)
     float *part, *drel_part;
     int64_t sb, sh, sn;
+    int32_t row_bytes;       // sn * sizeof(T): distance between the rows of two nodes
+    uint32_t slab_bytes;     // extent of one (batch, head) slab of Q/K/V/dout
+    uint32_t idx_bytes;      // extent of ia / ib
     int32_t BH, H, N, n_tokens;
     float scale;
     // adjacency: ptr[rows+1]; ia = other endpoint (col / t_src); ib = relative-position id
@@ -156,6 +159,41 @@ __device__ __forceinline__ float dot8(const Row<float>& x, const Row<float>& y, 
     c += x.b.x * y.b.x; c += x.b.y * y.b.y; c += x.b.z * y.b.z; c += x.b.w * y.b.w;
     return c;
 }
+// Gathers go through buffer loads: a 32-bit byte offset per lane against a
+// wave-uniform descriptor (cheap addressing, out-of-range offsets read 0), and,
+// being intrinsics rather than plain loads, they stay where the software pipeline
+// puts them instead of being sunk to their first use.
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+__device__ __forceinline__ rsrc_t make_rsrc(const void* p, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ int buf_i32(rsrc_t r, int byte_off) {
+    return (int)__builtin_amdgcn_raw_buffer_load_b32(r, byte_off, 0, 0);
+}
+__device__ __forceinline__ float2 buf_f2(rsrc_t r, int byte_off) {
+    const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(r, byte_off, 0, 0);
+    return make_float2(__uint_as_float(v.x), __uint_as_float(v.y));
+}
+__device__ __forceinline__ void buf_row(rsrc_t r, int byte_off, Row<bf16_t>& out) {
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, 0);
+    out.w = make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void buf_row(rsrc_t r, int byte_off, Row<float>& out) {
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, 0);
+    const u32x4 w = __builtin_amdgcn_raw_buffer_load_b128(r, byte_off + 16, 0, 0);
+    out.a = make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
+    out.b = make_float4(__uint_as_float(w.x), __uint_as_float(w.y), __uint_as_float(w.z), __uint_as_float(w.w));
+}
+// the lane's 8 features of the row of `node`
+template <typename T>
+__device__ __forceinline__ Row<T> gather_row(rsrc_t r, int node, int row_bytes, int lane_off) {
+    Row<T> out;
+    buf_row(r, (int)__umul24(node, row_bytes) + lane_off, out);
+    return out;
+}
+
 __device__ __forceinline__ uint32_t to_bf16_bits(float f) {  // round to nearest even
     uint32_t u = __float_as_uint(f);
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
@@ -188,22 +226,25 @@ struct TileWalk {
 // ---- forward --------------------------------------------------------------------
 // One segment [e0, e1) of row u (e1 > e0).  SPAN: the row is a span node.
 template <typename T, bool REL_LDS, bool SPAN>
-__device__ __forceinline__ void fwd_segment(const AttnArgs& a, const T* rel_s, int bh, int64_t base, int u, int e0,
-                                            int e1, int part, int lane) {
+__device__ __forceinline__ void fwd_segment(const AttnArgs& a, const T* rel_s, rsrc_t rK, rsrc_t rV, rsrc_t rIa,
+                                            rsrc_t rIb, int bh, int64_t base, int u, int e0, int e1, int part,
+                                            int lane) {
     const int slot = lane >> 3, sub = lane & 7;
-    const T* Kb = static_cast<const T*>(a.K) + base + sub * 8;
-    const T* Vb = static_cast<const T*>(a.V) + base + sub * 8;
+    const int lane_off = sub * 8 * (int)sizeof(T);
     const T* relg = static_cast<const T*>(a.rel) + sub * 8;
-    const int last = e1 - 1;
 
-    // indices two iterations ahead, rows one iteration ahead
-    int c0 = a.ia[min(e0 + slot, last)], c1 = a.ia[min(e0 + 8 + slot, last)];
+    // indices two iterations ahead, rows one iteration ahead.  Lanes past the end of
+    // the segment read the next rows' indices (or 0 past the array): valid nodes,
+    // and their contribution is masked.
+    int eo = (e0 + slot) * 4;
+    const int c0 = buf_i32(rIa, eo);
+    int c1 = buf_i32(rIa, eo + 32);
     int r0 = 0, r1 = 0;
     if (!SPAN) {
-        r0 = a.ib[min(e0 + slot, last)];
-        r1 = a.ib[min(e0 + 8 + slot, last)];
+        r0 = buf_i32(rIb, eo);
+        r1 = buf_i32(rIb, eo + 32);
     }
-    Row<T> k0 = load_row(Kb + (int64_t)c0 * a.sn), v0 = load_row(Vb + (int64_t)c0 * a.sn);
+    Row<T> k0 = gather_row<T>(rK, c0, a.row_bytes, lane_off), v0 = gather_row<T>(rV, c0, a.row_bytes, lane_off);
 
     const Row<T> q = load_row(static_cast<const T*>(a.Q) + base + (int64_t)u * a.sn + sub * 8);
     const float qscale = a.scale * kLog2e;
@@ -214,32 +255,49 @@ __device__ __forceinline__ void fwd_segment(const AttnArgs& a, const T* rel_s, i
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] = 0.f;
 
-    for (int eb = e0; eb < e1; eb += 8) {
-        const int c2 = a.ia[min(eb + 16 + slot, last)];
+    // One iteration: prefetch (indices of iteration +2, rows of iteration +1 into kn/vn),
+    // then work on the rows kc/vc fetched one iteration ago.  Called alternately with
+    // the two row buffers swapped, so nothing has to be copied between iterations.
+    auto step = [&](int eb, const Row<T>& kc, const Row<T>& vc, Row<T>& kn, Row<T>& vn) {
+        const int c2 = buf_i32(rIa, eo + 64);
         int r2 = 0;
-        if (!SPAN) r2 = a.ib[min(eb + 16 + slot, last)];
-        const Row<T> k1 = load_row(Kb + (int64_t)c1 * a.sn), v1 = load_row(Vb + (int64_t)c1 * a.sn);
+        if (!SPAN) r2 = buf_i32(rIb, eo + 64);
+        kn = gather_row<T>(rK, c1, a.row_bytes, lane_off);
+        vn = gather_row<T>(rV, c1, a.row_bytes, lane_off);
+        eo += 32;
 
         const bool valid = eb + slot < e1;
         float vv[8], d = 0.f;
-        if (!SPAN) d = dot8(q, REL_LDS ? load_row(rel_s + r0 * kD + sub * 8) : load_row(relg + (int64_t)r0 * kD), 0.f);
-        d = dot8(q, k0, d);
+        if (!SPAN) {
+            const int rid = valid ? r0 : 0;  // a masked lane may hold an id of some other row
+            d = dot8(q, REL_LDS ? load_row(rel_s + rid * kD + sub * 8) : load_row(relg + (int64_t)rid * kD), 0.f);
+        }
+        d = dot8(q, kc, d);
         float sc = sum8(d) * qscale + shift;
         sc = valid ? sc : kNegBig;
-        const float mn = fmaxf(m, sc);
-        const float corr = fast_exp2(m - mn);
-        const float p = valid ? fast_exp2(sc - mn) : 0.f;
-        unpack(v0, vv);
-        l = l * corr + p;
+        // online softmax with one exponential: of exp2(m - mn) and exp2(sc - mn) one is 1
+        const bool up = sc > m;
+        const float e = fast_exp2(up ? m - sc : sc - m);
+        const float corr = up ? e : 1.f;
+        const float p = valid ? (up ? 1.f : e) : 0.f;
+        m = up ? sc : m;
+        unpack(vc, vv);
+        l *= corr;
+        l += p;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) acc[i] = acc[i] * corr + p * vv[i];
-        m = mn;
-
-        k0 = k1;
-        v0 = v1;
+        for (int i = 0; i < 8; ++i) {
+            acc[i] *= corr;
+            acc[i] = fmaf(p, vv[i], acc[i]);
+        }
         c1 = c2;
         r0 = r1;
         r1 = r2;
+    };
+    Row<T> k1, v1;
+    for (int eb = e0; eb < e1; eb += 16) {
+        step(eb, k0, v0, k1, v1);
+        if (eb + 8 >= e1) break;
+        step(eb + 8, k1, v1, k0, v0);
     }
     // merge the 8 groups: common max, rescale, then sum
     const float mall = slots_max(m);
@@ -273,9 +331,12 @@ __global__ void __launch_bounds__(kThreads) fwd_kernel(const AttnArgs a) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform: row bookkeeping stays scalar
     const int nwaves = blockDim.x >> 6;
+    const rsrc_t rIa = make_rsrc(a.ia, a.idx_bytes), rIb = make_rsrc(a.ib, a.idx_bytes);
     for (TileWalk w(a.BH * a.num_tiles); w.t < w.t_end; w.t += w.step) {
         const int bh = w.t / a.num_tiles, tile = w.t - bh * a.num_tiles;
         const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
+        const rsrc_t rK = make_rsrc(static_cast<const T*>(a.K) + base, a.slab_bytes);
+        const rsrc_t rV = make_rsrc(static_cast<const T*>(a.V) + base, a.slab_bytes);
         const int s1 = a.tile_ptr[tile + 1];
         for (int s = a.tile_ptr[tile] + wave; s < s1; s += nwaves) {
             const int u = a.seg_row[s];
@@ -284,9 +345,9 @@ __global__ void __launch_bounds__(kThreads) fwd_kernel(const AttnArgs a) {
             const int part = a.seg_part[s];
             if (e1 <= e0) continue;  // no row of this adjacency is empty
             if (u >= a.n_tokens)
-                fwd_segment<T, REL_LDS, true>(a, rel_s, bh, base, u, e0, e1, part, lane);
+                fwd_segment<T, REL_LDS, true>(a, rel_s, rK, rV, rIa, rIb, bh, base, u, e0, e1, part, lane);
             else
-                fwd_segment<T, REL_LDS, false>(a, rel_s, bh, base, u, e0, e1, part, lane);
+                fwd_segment<T, REL_LDS, false>(a, rel_s, rK, rV, rIa, rIb, bh, base, u, e0, e1, part, lane);
         }
     }
 }
@@ -322,21 +383,22 @@ __global__ void __launch_bounds__(256) fwd_merge_kernel(const AttnArgs a, const 
 // so one pass over the row gives delta exactly (in fp32, not through the rounded
 // `out`) and dQ.  For a span row r_anc drops out of dQ because the dS of a row sum to 0.
 template <typename T, bool REL_LDS, bool SPAN>
-__device__ __forceinline__ void bwd_q_segment(const AttnArgs& a, const T* rel_s, int bh, int64_t base, int u, int e0,
-                                              int e1, int part, int lane) {
+__device__ __forceinline__ void bwd_q_segment(const AttnArgs& a, const T* rel_s, rsrc_t rK, rsrc_t rV, rsrc_t rIa,
+                                              rsrc_t rIb, int bh, int64_t base, int u, int e0, int e1, int part,
+                                              int lane) {
     const int slot = lane >> 3, sub = lane & 7;
-    const T* Kb = static_cast<const T*>(a.K) + base + sub * 8;
-    const T* Vb = static_cast<const T*>(a.V) + base + sub * 8;
+    const int lane_off = sub * 8 * (int)sizeof(T);
     const T* relg = static_cast<const T*>(a.rel) + sub * 8;
-    const int last = e1 - 1;
 
-    int c0 = a.ia[min(e0 + slot, last)], c1 = a.ia[min(e0 + 8 + slot, last)];
+    int eo = (e0 + slot) * 4;
+    const int c0 = buf_i32(rIa, eo);
+    int c1 = buf_i32(rIa, eo + 32);
     int r0 = 0, r1 = 0;
     if (!SPAN) {
-        r0 = a.ib[min(e0 + slot, last)];
-        r1 = a.ib[min(e0 + 8 + slot, last)];
+        r0 = buf_i32(rIb, eo);
+        r1 = buf_i32(rIb, eo + 32);
     }
-    Row<T> k0 = load_row(Kb + (int64_t)c0 * a.sn), v0 = load_row(Vb + (int64_t)c0 * a.sn);
+    Row<T> k0 = gather_row<T>(rK, c0, a.row_bytes, lane_off), v0 = gather_row<T>(rV, c0, a.row_bytes, lane_off);
 
     float qs[8];
     load8(static_cast<const T*>(a.Q) + base + (int64_t)u * a.sn + sub * 8, qs);
@@ -357,21 +419,23 @@ __device__ __forceinline__ void bwd_q_segment(const AttnArgs& a, const T* rel_s,
 #pragma unroll
     for (int i = 0; i < 8; ++i) A[i] = Bv[i] = 0.f;
 
-    for (int eb = e0; eb < e1; eb += 8) {
-        const int c2 = a.ia[min(eb + 16 + slot, last)];
+    auto step = [&](int eb, const Row<T>& kc, const Row<T>& vc, Row<T>& kn, Row<T>& vn) {
+        const int c2 = buf_i32(rIa, eo + 64);
         int r2 = 0;
-        if (!SPAN) r2 = a.ib[min(eb + 16 + slot, last)];
-        const Row<T> k1 = load_row(Kb + (int64_t)c1 * a.sn), v1 = load_row(Vb + (int64_t)c1 * a.sn);
+        if (!SPAN) r2 = buf_i32(rIb, eo + 64);
+        kn = gather_row<T>(rK, c1, a.row_bytes, lane_off);
+        vn = gather_row<T>(rV, c1, a.row_bytes, lane_off);
 
         const bool valid = eb + slot < e1;
         float kk[8];
-        unpack(k0, kk);
+        unpack(kc, kk);
         if (!SPAN) {
             float r[8];
+            const int rid = valid ? r0 : 0;  // a masked lane may hold an id of some other row
             if (REL_LDS)
-                load8(rel_s + r0 * kD + sub * 8, r);
+                load8(rel_s + rid * kD + sub * 8, r);
             else
-                load8(relg + (int64_t)r0 * kD, r);
+                load8(relg + (int64_t)rid * kD, r);
 #pragma unroll
             for (int i = 0; i < 8; ++i) kk[i] += r[i];
         }
@@ -379,22 +443,27 @@ __device__ __forceinline__ void bwd_q_segment(const AttnArgs& a, const T* rel_s,
 #pragma unroll
         for (int i = 0; i < 8; ++i) d += qs[i] * kk[i];
         const float sc = sum8(d) + shift;
-        const float dP = sum8(dot8(g, v0, 0.f));
+        const float dP = sum8(dot8(g, vc, 0.f));
         const float p = valid ? fast_exp2(sc - lse2) : 0.f;
         const float wgt = p * dP;
         dl += wgt;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            A[i] += wgt * kk[i];
-            Bv[i] += p * kk[i];
+            A[i] = fmaf(wgt, kk[i], A[i]);
+            Bv[i] = fmaf(p, kk[i], Bv[i]);
         }
         // what d_rel needs of this edge (dS_e = w_e - delta_u p_e once delta_u is known)
-        if (!SPAN && valid && sub == 0) a.wp[(int64_t)bh * a.e_tok + eb + slot] = make_float2(wgt, p);
-        k0 = k1;
-        v0 = v1;
+        if (!SPAN && valid && sub == 0) a.wp[(int64_t)bh * a.e_tok + (eo >> 2)] = make_float2(wgt, p);
+        eo += 32;
         c1 = c2;
         r0 = r1;
         r1 = r2;
+    };
+    Row<T> k1, v1;
+    for (int eb = e0; eb < e1; eb += 16) {
+        step(eb, k0, v0, k1, v1);
+        if (eb + 8 >= e1) break;
+        step(eb + 8, k1, v1, k0, v0);
     }
     dl = slots_sum(dl);
     const int col = sub * 8 + slot_elem(lane);
@@ -422,9 +491,12 @@ __global__ void __launch_bounds__(kThreads) bwd_q_kernel(const AttnArgs a) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nwaves = blockDim.x >> 6;
+    const rsrc_t rIa = make_rsrc(a.ia, a.idx_bytes), rIb = make_rsrc(a.ib, a.idx_bytes);
     for (TileWalk w(a.BH * a.num_tiles); w.t < w.t_end; w.t += w.step) {
         const int bh = w.t / a.num_tiles, tile = w.t - bh * a.num_tiles;
         const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
+        const rsrc_t rK = make_rsrc(static_cast<const T*>(a.K) + base, a.slab_bytes);
+        const rsrc_t rV = make_rsrc(static_cast<const T*>(a.V) + base, a.slab_bytes);
         const int s1 = a.tile_ptr[tile + 1];
         for (int s = a.tile_ptr[tile] + wave; s < s1; s += nwaves) {
             const int u = a.seg_row[s];
@@ -433,9 +505,9 @@ __global__ void __launch_bounds__(kThreads) bwd_q_kernel(const AttnArgs a) {
             const int part = a.seg_part[s];
             if (e1 <= e0) continue;
             if (u >= a.n_tokens)
-                bwd_q_segment<T, REL_LDS, true>(a, rel_s, bh, base, u, e0, e1, part, lane);
+                bwd_q_segment<T, REL_LDS, true>(a, rel_s, rK, rV, rIa, rIb, bh, base, u, e0, e1, part, lane);
             else
-                bwd_q_segment<T, REL_LDS, false>(a, rel_s, bh, base, u, e0, e1, part, lane);
+                bwd_q_segment<T, REL_LDS, false>(a, rel_s, rK, rV, rIa, rIb, bh, base, u, e0, e1, part, lane);
         }
     }
 }
@@ -465,13 +537,12 @@ __global__ void __launch_bounds__(256) bwd_q_merge_kernel(const AttnArgs a, cons
 // (lse_u, delta_u) of its queries u are gathered.  No atomics: every key row is
 // reduced by one wavefront (or by the merge kernel, in segment order).
 template <typename T, bool REL_LDS>
-__device__ __forceinline__ void bwd_kv_segment(const AttnArgs& a, const T* rel_s, int bh, int64_t base, int v, int e0,
-                                               int e1, int part, int lane) {
+__device__ __forceinline__ void bwd_kv_segment(const AttnArgs& a, const T* rel_s, rsrc_t rQ, rsrc_t rG, rsrc_t rS,
+                                               rsrc_t rIa, rsrc_t rIb, int bh, int64_t base, int v, int e0, int e1,
+                                               int part, int lane) {
     const int slot = lane >> 3, sub = lane & 7;
-    const T* Qb = static_cast<const T*>(a.Q) + base + sub * 8;
-    const T* Gb = static_cast<const T*>(a.dout) + base + sub * 8;
+    const int lane_off = sub * 8 * (int)sizeof(T);
     const T* relg = static_cast<const T*>(a.rel) + sub * 8;
-    const float2* stat_b = a.stat + (int64_t)bh * a.N;
     const float qscale = a.scale * kLog2e;
 
     float dk[8], dv[8];
@@ -479,41 +550,49 @@ __device__ __forceinline__ void bwd_kv_segment(const AttnArgs& a, const T* rel_s
     for (int i = 0; i < 8; ++i) dk[i] = dv[i] = 0.f;
 
     if (e1 > e0) {
-        const int last = e1 - 1;
-        int u0 = a.ia[min(e0 + slot, last)], u1 = a.ia[min(e0 + 8 + slot, last)];
-        int r0 = a.ib[min(e0 + slot, last)], r1 = a.ib[min(e0 + 8 + slot, last)];
-        Row<T> q0 = load_row(Qb + (int64_t)u0 * a.sn), g0 = load_row(Gb + (int64_t)u0 * a.sn);
-        float2 st0 = stat_b[u0];
+        int eo = (e0 + slot) * 4;
+        const int u0 = buf_i32(rIa, eo);
+        int u1 = buf_i32(rIa, eo + 32);
+        int r0 = buf_i32(rIb, eo), r1 = buf_i32(rIb, eo + 32);
+        Row<T> q0 = gather_row<T>(rQ, u0, a.row_bytes, lane_off), g0 = gather_row<T>(rG, u0, a.row_bytes, lane_off);
+        float2 st0 = buf_f2(rS, u0 * 8);
         const Row<T> kk = load_row(static_cast<const T*>(a.K) + base + (int64_t)v * a.sn + sub * 8);
         const Row<T> vv = load_row(static_cast<const T*>(a.V) + base + (int64_t)v * a.sn + sub * 8);
 
-        for (int eb = e0; eb < e1; eb += 8) {
-            const int u2 = a.ia[min(eb + 16 + slot, last)];
-            const int r2 = a.ib[min(eb + 16 + slot, last)];
-            const Row<T> q1 = load_row(Qb + (int64_t)u1 * a.sn), g1 = load_row(Gb + (int64_t)u1 * a.sn);
-            const float2 st1 = stat_b[u1];
+        auto step = [&](int eb, const Row<T>& qc, const Row<T>& gc, const float2& stc, Row<T>& qn, Row<T>& gn,
+                        float2& stn) {
+            const int u2 = buf_i32(rIa, eo + 64);
+            const int r2 = buf_i32(rIb, eo + 64);
+            qn = gather_row<T>(rQ, u1, a.row_bytes, lane_off);
+            gn = gather_row<T>(rG, u1, a.row_bytes, lane_off);
+            stn = buf_f2(rS, u1 * 8);
+            eo += 32;
 
             const bool valid = eb + slot < e1;
             float q[8], g[8];
-            float d = dot8(q0, REL_LDS ? load_row(rel_s + r0 * kD + sub * 8) : load_row(relg + (int64_t)r0 * kD), 0.f);
-            d = dot8(q0, kk, d);
+            float d = dot8(qc, REL_LDS ? load_row(rel_s + r0 * kD + sub * 8) : load_row(relg + (int64_t)r0 * kD), 0.f);
+            d = dot8(qc, kk, d);
             const float sc = sum8(d) * qscale;
-            const float dP = sum8(dot8(g0, vv, 0.f));
-            unpack(q0, q);
-            unpack(g0, g);
-            const float p = valid ? fast_exp2(sc - st0.x) : 0.f;
-            const float dS = p * (dP - st0.y);
+            const float dP = sum8(dot8(gc, vv, 0.f));
+            unpack(qc, q);
+            unpack(gc, g);
+            const float p = valid ? fast_exp2(sc - stc.x) : 0.f;
+            const float dS = p * (dP - stc.y);
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                dk[i] += dS * q[i];
-                dv[i] += p * g[i];
+                dk[i] = fmaf(dS, q[i], dk[i]);
+                dv[i] = fmaf(p, g[i], dv[i]);
             }
-            q0 = q1;
-            g0 = g1;
-            st0 = st1;
             u1 = u2;
             r0 = r1;
             r1 = r2;
+        };
+        Row<T> q1, g1;
+        float2 st1;
+        for (int eb = e0; eb < e1; eb += 16) {
+            step(eb, q0, g0, st0, q1, g1, st1);
+            if (eb + 8 >= e1) break;
+            step(eb + 8, q1, g1, st1, q0, g0, st0);
         }
     }
     const float tk = reduce_slots8(dk, lane), tv = reduce_slots8(dv, lane);
@@ -539,15 +618,19 @@ __global__ void __launch_bounds__(kThreads) bwd_kv_kernel(const AttnArgs a) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nwaves = blockDim.x >> 6;
+    const rsrc_t rIa = make_rsrc(a.ia, a.idx_bytes), rIb = make_rsrc(a.ib, a.idx_bytes);
     for (TileWalk w(a.BH * a.num_tiles); w.t < w.t_end; w.t += w.step) {
         const int bh = w.t / a.num_tiles, tile = w.t - bh * a.num_tiles;
         const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
+        const rsrc_t rQ = make_rsrc(static_cast<const T*>(a.Q) + base, a.slab_bytes);
+        const rsrc_t rG = make_rsrc(static_cast<const T*>(a.dout) + base, a.slab_bytes);
+        const rsrc_t rS = make_rsrc(a.stat + (int64_t)bh * a.N, (uint32_t)a.N * 8u);
         const int s1 = a.tile_ptr[tile + 1];
         for (int s = a.tile_ptr[tile] + wave; s < s1; s += nwaves) {
             const int v = a.seg_row[s];
             const int e0 = a.seg_begin[s];
             const int e1 = min(e0 + kSeg, a.ptr[v + 1]);
-            bwd_kv_segment<T, REL_LDS>(a, rel_s, bh, base, v, e0, e1, a.seg_part[s], lane);
+            bwd_kv_segment<T, REL_LDS>(a, rel_s, rQ, rG, rS, rIa, rIb, bh, base, v, e0, e1, a.seg_part[s], lane);
         }
     }
 }
@@ -695,6 +778,11 @@ int check_shape(const bpt_graph* g, const bpt_shape_t* s) {
     if ((int64_t)s->B * s->H > (int64_t)INT32_MAX / std::max(g->fwd.num_tiles, g->tr.num_tiles))
         return BPT_ERR_UNSUPPORTED;
     if ((int64_t)s->B * s->H * g->num_nodes > (int64_t)1 << 40) return BPT_ERR_UNSUPPORTED;
+    if (g->num_edges >= ((int64_t)1 << 29)) return BPT_ERR_UNSUPPORTED;  // 32-bit byte offsets into the edge arrays
+    // the gathers address one (batch, head) slab with 32-bit byte offsets
+    const int64_t es = s->dtype == BPT_BF16 ? 2 : 4;
+    if (s->stride_n * es >= (1 << 24) || (int64_t)g->num_nodes * s->stride_n * es >= ((int64_t)1 << 31))
+        return BPT_ERR_UNSUPPORTED;
     return BPT_OK;
 }
 
@@ -733,6 +821,10 @@ void fill_common(AttnArgs& a, const bpt_graph* g, const bpt_shape_t* s) {
     a.n_tokens = g->n;
     a.scale = s->scale > 0.f ? s->scale : 0.125f;  // 1/sqrt(64)
     a.rel_rows = g->num_levels * g->rel_width;
+    const int64_t es = s->dtype == BPT_BF16 ? 2 : 4;
+    a.row_bytes = (int32_t)(s->stride_n * es);
+    a.slab_bytes = (uint32_t)(((int64_t)(g->num_nodes - 1) * s->stride_n + kD) * es);
+    a.idx_bytes = (uint32_t)(g->num_edges * 4);
 }
 
 void use_schedule(AttnArgs& a, const Schedule& sc) {
