@@ -715,6 +715,127 @@ __global__ void __launch_bounds__(kThreads) rel_grad_kernel(const AttnArgs a) {
     }
 }
 
+
+// The same contraction on the matrix cores, for bf16 tensors.  dS is fp32; it is
+// split into two bf16 numbers (hi + lo carries 16 mantissa bits) so that the products
+// with the bf16 query features are exact and accumulate in fp32.  Per block of 32
+// token rows the workgroup keeps DS^T (hi and lo, [id][row]) and Q^T ([feature][row])
+// in LDS, rows padded to 80 bytes so that the 16-byte operand reads of 8 lanes fall
+// into 8 different bank quads.  v_mfma_f32_16x16x32_bf16: A[m][k] sits in lane
+// m + 16*(k/8) (8 consecutive k per lane), B[k][n] in lane n + 16*(k/8), and
+// C[m][n] in lane n + 16*(m/4), register m%4.  Here m = relative-position id,
+// n = feature, k = row of the block.  Wavefront w owns the 16-id chunks w and w+8
+// of the workgroup's 256 ids (blockIdx.y selects the 256).
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+constexpr int kRgRows = 32;     // token rows per block = K of one MFMA
+constexpr int kRgStride = 40;   // bf16 elements per LDS row (32 + padding)
+constexpr int kRgIds = 256;     // ids per workgroup
+
+__global__ void __launch_bounds__(kThreads) rel_grad_mfma_kernel(const AttnArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int id0 = blockIdx.y * kRgIds;
+    const int nids = min(kRgIds, (a.drel_rows - id0 + 15) & ~15);   // ids of this workgroup, padded to 16
+    bf16_t* ds_hi = reinterpret_cast<bf16_t*>(smem);                // [nids][kRgStride]
+    bf16_t* ds_lo = ds_hi + nids * kRgStride;
+    bf16_t* q_t = ds_lo + nids * kRgStride;                         // [kD][kRgStride]
+    __shared__ int row_s[kRgRows + 1];
+    __shared__ float delta_s[kRgRows];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int g = lane >> 4, j = lane & 15;
+    const int blocks_per_bh = (a.n_tokens + kRgRows - 1) / kRgRows;
+    const int total = a.BH * blocks_per_bh;
+    const int nchunks = nids >> 4;
+
+    f32x4_t acc[2][4];
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int f = 0; f < 4; ++f) acc[c][f] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    for (int blk = blockIdx.x; blk < total; blk += gridDim.x) {
+        const int bh = blk / blocks_per_bh, row0 = (blk - bh * blocks_per_bh) * kRgRows;
+        const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
+        // clear DS^T (hi and lo are adjacent)
+        for (int i = threadIdx.x * 8; i < 2 * nids * kRgStride; i += blockDim.x * 8)
+            *reinterpret_cast<uint4*>(ds_hi + i) = make_uint4(0u, 0u, 0u, 0u);
+        // Q^T: thread -> (row, 8 features); rows past the sequence are zero
+        for (int i = threadIdx.x; i < kRgRows * 8; i += blockDim.x) {
+            const int r = i >> 3, c = (i & 7) * 8;
+            uint4 w = make_uint4(0u, 0u, 0u, 0u);
+            if (row0 + r < a.n_tokens)
+                w = *reinterpret_cast<const uint4*>(static_cast<const bf16_t*>(a.Q) + base +
+                                                    (int64_t)(row0 + r) * a.sn + c);
+            const uint32_t x[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                q_t[(c + 2 * t) * kRgStride + r] = (bf16_t)(x[t] & 0xFFFFu);
+                q_t[(c + 2 * t + 1) * kRgStride + r] = (bf16_t)(x[t] >> 16);
+            }
+        }
+        // row pointers and delta of the block's rows
+        if (threadIdx.x <= kRgRows) row_s[threadIdx.x] = a.ptr[min(row0 + (int)threadIdx.x, a.n_tokens)];
+        if (threadIdx.x < kRgRows && row0 + (int)threadIdx.x < a.n_tokens)
+            delta_s[threadIdx.x] = a.stat[(int64_t)bh * a.N + row0 + threadIdx.x].y;
+        __syncthreads();
+        // scatter dS = w - delta*p of every edge of the block's rows; the edges of the block
+        // are contiguous in the CSR, one thread per edge, its row found by bisection
+        const float2* wp_b = a.wp + (int64_t)bh * a.e_tok;
+        const int e_end = row_s[kRgRows];
+        for (int e = row_s[0] + threadIdx.x; e < e_end; e += blockDim.x) {
+            const int id = a.ib[e] - id0;
+            const float2 x = wp_b[e];
+            int r = 0;
+#pragma unroll
+            for (int w = kRgRows / 2; w > 0; w >>= 1)
+                if (row_s[r + w] <= e) r += w;
+            if (id >= 0 && id < nids) {
+                const float ds = x.x - delta_s[r] * x.y;
+                const uint32_t hi = to_bf16_bits(ds);
+                const uint32_t lo = to_bf16_bits(ds - __uint_as_float(hi << 16));
+                ds_hi[id * kRgStride + r] = (bf16_t)hi;
+                ds_lo[id * kRgStride + r] = (bf16_t)lo;
+            }
+        }
+        __syncthreads();
+        bf16x8_t qb[4];
+#pragma unroll
+        for (int f = 0; f < 4; ++f)
+            qb[f] = *reinterpret_cast<const bf16x8_t*>(q_t + (16 * f + j) * kRgStride + 8 * g);
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const int chunk = wave + kWaves * c;
+            if (chunk < nchunks) {
+                const int off = (16 * chunk + j) * kRgStride + 8 * g;
+                const bf16x8_t ah = *reinterpret_cast<const bf16x8_t*>(ds_hi + off);
+                const bf16x8_t al = *reinterpret_cast<const bf16x8_t*>(ds_lo + off);
+#pragma unroll
+                for (int f = 0; f < 4; ++f) {
+                    acc[c][f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, qb[f], acc[c][f], 0, 0, 0);
+                    acc[c][f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al, qb[f], acc[c][f], 0, 0, 0);
+                }
+            }
+        }
+        __syncthreads();
+    }
+    // this workgroup's copy: [gridDim.x][drel_rows][kD]
+    float* dst = a.drel_part + (int64_t)blockIdx.x * a.drel_rows * kD;
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        const int chunk = wave + kWaves * c;
+        if (chunk < nchunks) {
+#pragma unroll
+            for (int f = 0; f < 4; ++f)
+#pragma unroll
+                for (int m = 0; m < 4; ++m) {
+                    const int id = id0 + 16 * chunk + 4 * g + m;
+                    if (id < a.drel_rows) dst[id * kD + 16 * f + j] = acc[c][f][m] * a.scale;
+                }
+        }
+    }
+}
+
 // key nodes cut into several segments: sum the (dK, dV) partials in segment order
 __global__ void __launch_bounds__(256) bwd_kv_merge_kernel(const AttnArgs a, const int32_t* __restrict__ multi_row,
                                                            const int32_t* __restrict__ multi_ptr, int num_multi) {
@@ -734,21 +855,33 @@ __global__ void __launch_bounds__(256) bwd_kv_merge_kernel(const AttnArgs a, con
 }
 
 // d_rel = sum of the workgroups' copies, in a fixed order; rows the copies do not
-// cover are zero.  One workgroup per row of 64 features: 4 wavefronts each sum a
-// quarter of the copies (lane = feature, coalesced 256-byte reads), then combine.
-__global__ void __launch_bounds__(256) drel_reduce_kernel(const float* __restrict__ parts, int num_parts,
-                                                          int covered_rows, float* __restrict__ d_rel) {
-    __shared__ float s[4][kD];
+// cover are zero.  One workgroup per row of 64 features: 16 wavefronts each sum a
+// sixteenth of the copies (lane = feature, coalesced 256-byte reads, four
+// independent partial sums in flight), then combine in a fixed tree.
+__global__ void __launch_bounds__(1024) drel_reduce_kernel(const float* __restrict__ parts, int num_parts,
+                                                           int covered_rows, float* __restrict__ d_rel) {
+    __shared__ float s[16][kD];
     const int row = blockIdx.x, lane = threadIdx.x & 63, grp = threadIdx.x >> 6;
-    float acc = 0.f;
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
     if (row < covered_rows) {
         const float* src = parts + (int64_t)row * kD + lane;
         const int64_t stride = (int64_t)covered_rows * kD;
-        for (int p = grp; p < num_parts; p += 4) acc += src[p * stride];
+        int p = grp;
+        for (; p + 48 < num_parts; p += 64) {
+            a0 += src[p * stride];
+            a1 += src[(p + 16) * stride];
+            a2 += src[(p + 32) * stride];
+            a3 += src[(p + 48) * stride];
+        }
+        for (; p < num_parts; p += 16) a0 += src[p * stride];
     }
-    s[grp][lane] = acc;
+    s[grp][lane] = (a0 + a1) + (a2 + a3);
     __syncthreads();
-    if (grp == 0) d_rel[row * kD + lane] = (s[0][lane] + s[1][lane]) + (s[2][lane] + s[3][lane]);
+    for (int w = 8; w > 0; w >>= 1) {
+        if (grp < w) s[grp][lane] += s[grp + w][lane];
+        __syncthreads();
+    }
+    if (grp == 0) d_rel[row * kD + lane] = s[0][lane];
 }
 
 // ---- host side --------------------------------------------------------------------
@@ -867,6 +1000,7 @@ int run_fwd(const bpt_graph* g, AttnArgs& a, hipStream_t st) {
 // Workspace layout of the backward and the launch shape of rel_grad_kernel.
 struct BwdPlan {
     int drel_rows = 0;        // d_rel rows token rows can touch
+    bool drel_mfma = false;   // bf16 tensors: rel_grad_mfma_kernel; fp32: rel_grad_kernel
     int drel_ipw = 32;        // ids per wavefront: 8, 16 or 32
     int drel_block = 32;      // token rows per block
     int drel_grid_x = 8, drel_grid_y = 1;
@@ -879,13 +1013,22 @@ int plan_bwd(const bpt_graph* g, const bpt_shape_t* s, BwdPlan* p) {
     int rc = device_limits(g, &lim);
     if (rc) return rc;
     p->drel_rows = g->ctx_levels * g->rel_width;
-    p->drel_ipw = p->drel_rows <= 64 ? 8 : p->drel_rows <= 128 ? 16 : 32;
-    const int chunk = p->drel_ipw * kWaves;
-    p->drel_block = std::min(g->n, chunk > 128 ? 32 : 64);
-    p->drel_lds = (size_t)p->drel_block * (chunk + kD) * sizeof(float);
-    p->drel_grid_y = (p->drel_rows + chunk - 1) / chunk;
+    int64_t blocks;
+    if (s->dtype == BPT_BF16) {  // matrix-core kernel
+        p->drel_mfma = true;
+        const int nids = std::min(kRgIds, (p->drel_rows + 15) & ~15);
+        p->drel_lds = ((size_t)2 * nids + kD) * kRgStride * sizeof(bf16_t);
+        p->drel_grid_y = (p->drel_rows + kRgIds - 1) / kRgIds;
+        blocks = (int64_t)s->B * s->H * ((g->n + kRgRows - 1) / kRgRows);
+    } else {
+        p->drel_ipw = p->drel_rows <= 64 ? 8 : p->drel_rows <= 128 ? 16 : 32;
+        const int chunk = p->drel_ipw * kWaves;
+        p->drel_block = std::min(g->n, chunk > 128 ? 32 : 64);
+        p->drel_lds = (size_t)p->drel_block * (chunk + kD) * sizeof(float);
+        p->drel_grid_y = (p->drel_rows + chunk - 1) / chunk;
+        blocks = (int64_t)s->B * s->H * (g->n / p->drel_block);
+    }
     const int per_cu = (int)std::max<size_t>(1, std::min<size_t>(4, lim.lds / p->drel_lds));
-    const int64_t blocks = (int64_t)s->B * s->H * (g->n / p->drel_block);
     p->drel_grid_x = (int)std::max<int64_t>(1, std::min<int64_t>(blocks, (int64_t)lim.cus * per_cu / p->drel_grid_y));
     const size_t bh = (size_t)s->B * s->H;
     size_t off = 0;
@@ -945,10 +1088,16 @@ int run_bwd_q(const bpt_graph* g, const BwdPlan& p, AttnArgs& a, hipStream_t st)
                            g->fwd.multi_ptr, g->fwd.num_multi);
         BPT_HIP(hipGetLastError());
     }
-    rc = p.drel_ipw == 8 ? launch_rel_grad<T, 8>(p, st, a)
-                         : p.drel_ipw == 16 ? launch_rel_grad<T, 16>(p, st, a) : launch_rel_grad<T, 32>(p, st, a);
+    if (p.drel_mfma) {
+        hipLaunchKernelGGL(rel_grad_mfma_kernel, dim3(p.drel_grid_x, p.drel_grid_y), dim3(kThreads), p.drel_lds, st, a);
+        BPT_HIP(hipGetLastError());
+        rc = BPT_OK;
+    } else {
+        rc = p.drel_ipw == 8 ? launch_rel_grad<T, 8>(p, st, a)
+                             : p.drel_ipw == 16 ? launch_rel_grad<T, 16>(p, st, a) : launch_rel_grad<T, 32>(p, st, a);
+    }
     if (rc) return rc;
-    hipLaunchKernelGGL(drel_reduce_kernel, dim3(a.rel_rows), dim3(256), 0, st, a.drel_part, p.drel_grid_x,
+    hipLaunchKernelGGL(drel_reduce_kernel, dim3(a.rel_rows), dim3(1024), 0, st, a.drel_part, p.drel_grid_x,
                        p.drel_rows, a.d_rel);
     BPT_HIP(hipGetLastError());
     return BPT_OK;
