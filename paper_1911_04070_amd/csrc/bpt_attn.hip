@@ -732,13 +732,33 @@ constexpr int kRgRows = 32;     // token rows per block = K of one MFMA
 constexpr int kRgStride = 40;   // bf16 elements per LDS row (32 + padding)
 constexpr int kRgIds = 256;     // ids per workgroup
 
+// ADD_DQ: also add the relative-position part of dQ of the block's rows,
+// dQ_rel = scale * DS Rel (the tile kernel leaves it out); needs all ids in one
+// workgroup (gridDim.y == 1).  Wavefront w computes rows 16*(w/4).. and features
+// 16*(w%4).. of the 32 x 64 block: A = DS (read transposed out of DS^T), B = Rel^T.
+template <bool ADD_DQ>
 __global__ void __launch_bounds__(kThreads) rel_grad_mfma_kernel(const AttnArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int id0 = blockIdx.y * kRgIds;
-    const int nids = min(kRgIds, (a.drel_rows - id0 + 15) & ~15);   // ids of this workgroup, padded to 16
+    const int nids = min(kRgIds, (a.drel_rows - id0 + 31) & ~31);   // ids of this workgroup, padded to 32
     bf16_t* ds_hi = reinterpret_cast<bf16_t*>(smem);                // [nids][kRgStride]
     bf16_t* ds_lo = ds_hi + nids * kRgStride;
     bf16_t* q_t = ds_lo + nids * kRgStride;                         // [kD][kRgStride]
+    bf16_t* rel_t = q_t + kD * kRgStride;                           // [kD][nids + 8]   (ADD_DQ)
+    const int rt_stride = nids + 8;
+    if (ADD_DQ) {
+        for (int i = threadIdx.x; i < nids * 8; i += blockDim.x) {
+            const int id = i >> 3, c = (i & 7) * 8;
+            uint4 w = make_uint4(0u, 0u, 0u, 0u);
+            if (id < a.drel_rows) w = *reinterpret_cast<const uint4*>(static_cast<const bf16_t*>(a.rel) + (int64_t)id * kD + c);
+            const uint32_t x[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                rel_t[(c + 2 * t) * rt_stride + id] = (bf16_t)(x[t] & 0xFFFFu);
+                rel_t[(c + 2 * t + 1) * rt_stride + id] = (bf16_t)(x[t] >> 16);
+            }
+        }
+    }
     __shared__ int row_s[kRgRows + 1];
     __shared__ float delta_s[kRgRows];
     const int lane = threadIdx.x & 63;
@@ -799,6 +819,25 @@ __global__ void __launch_bounds__(kThreads) rel_grad_mfma_kernel(const AttnArgs 
             }
         }
         __syncthreads();
+        if (ADD_DQ) {
+            const int mc = wave >> 2, fc = wave & 3;
+            f32x4_t dq = {0.f, 0.f, 0.f, 0.f};
+            for (int ks = 0; ks < nids; ks += 32) {
+                const bf16_t* col = ds_hi + (ks + 8 * g) * kRgStride + 16 * mc + j;   // DS[row][id] = DS^T[id][row]
+                u32x4 x;
+                x.x = (uint32_t)col[0] | ((uint32_t)col[kRgStride] << 16);
+                x.y = (uint32_t)col[2 * kRgStride] | ((uint32_t)col[3 * kRgStride] << 16);
+                x.z = (uint32_t)col[4 * kRgStride] | ((uint32_t)col[5 * kRgStride] << 16);
+                x.w = (uint32_t)col[6 * kRgStride] | ((uint32_t)col[7 * kRgStride] << 16);
+                const bf16x8_t rb = *reinterpret_cast<const bf16x8_t*>(rel_t + (16 * fc + j) * rt_stride + ks + 8 * g);
+                dq = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, x), rb, dq, 0, 0, 0);
+            }
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                const int row = row0 + 16 * mc + 4 * g + m;
+                if (row < a.n_tokens) a.dQ[base + (int64_t)row * a.sn + 16 * fc + j] += a.scale * dq[m];
+            }
+        }
         bf16x8_t qb[4];
 #pragma unroll
         for (int f = 0; f < 4; ++f)
@@ -833,6 +872,387 @@ __global__ void __launch_bounds__(kThreads) rel_grad_mfma_kernel(const AttnArgs 
                     if (id < a.drel_rows) dst[id * kD + 16 * f + j] = acc[c][f][m] * a.scale;
                 }
         }
+    }
+}
+
+
+// ---- forward over dense tiles of token rows, on the matrix cores (bf16) ---------------
+// A wavefront computes 16 consecutive token rows against the union U of their key
+// nodes (tile metadata of the graph).  Consecutive tokens share almost all coarse
+// neighbours, so the 16 x |U| score tile is more than half full and the products
+// Q K^T and P V are real dense contractions:
+//   S^T chunk [16 columns x 16 tokens] = K_chunk (A, rows straight from memory) x Q^T (B),
+//   bias^T [ids x 16 tokens]            = Rel (A, from LDS)                    x Q^T (B),
+//   out [16 tokens x 64]               += P (A) x V_chunk (B, transposed through LDS).
+// With v_mfma_f32_16x16x32_bf16 the result C[m][n] lives in lane n + 16*(m/4),
+// register m%4 -- for S^T that is token n = lane%16 and columns 4*(lane/16)..+3, which
+// is exactly the A-operand layout P needs for the second product (A[m][k] in lane
+// m + 16*(k/8)) once the columns of two chunks are interleaved as k = 8g+i:
+// i<4 -> chunk 2c, column 4g+i; i>=4 -> chunk 2c+1, column 4g+i-4.  The feature
+// dimension of the first product is permuted the same way in both operands (lane
+// group g owns features 16g..16g+15), which leaves the dot products unchanged.
+// Softmax runs online over groups of 8 chunks; masked and padding columns carry
+// the id -1 in the tile map.
+constexpr int kTileThreads = 256;
+constexpr int kTileWaves = kTileThreads / 64;
+constexpr int kRelStride = 72;   // bf16 per LDS row of the compact table (64 + padding: 144 B)
+constexpr int kVStride = 68;     // bf16 per LDS row of a staged V row (136 B)
+constexpr int kGroup = 8;        // chunks per softmax group
+
+struct TileArgs {
+    const bf16_t *Q, *K, *V, *rel;
+    bf16_t* out;
+    float* lse;
+    int64_t sb, sh, sn;
+    int32_t BH, H, N;
+    float scale;
+    const int32_t *chunk_ptr, *cols, *cid_to_id;
+    const int16_t* map;
+    int32_t num_tiles, num_cids, cid_pad, bias_stride;
+    int32_t row_bytes;
+    uint32_t slab_bytes;
+    // backward, query side
+    const bf16_t* dout;
+    const float* lse_r;
+    float* dQ;
+    float2 *stat, *wp;
+    int64_t e_tok;
+    const int16_t* emap;
+    const int32_t* row_ptr;
+};
+
+__device__ __forceinline__ void wave_lds_sync() {  // order LDS traffic between the lanes of one wavefront
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+__device__ __forceinline__ bf16x8_t as_bf16x8(const Row<bf16_t>& r) { return __builtin_bit_cast(bf16x8_t, r.w); }
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) { return to_bf16_bits(lo) | (to_bf16_bits(hi) << 16); }
+// two floats -> packed bf16 pair of their leading parts and packed bf16 pair of the remainders
+__device__ __forceinline__ void split_pack(float x, float y, uint32_t& hi, uint32_t& lo) {
+    const uint32_t xh = to_bf16_bits(x), yh = to_bf16_bits(y);
+    hi = xh | (yh << 16);
+    lo = pack_bf16(x - __uint_as_float(xh << 16), y - __uint_as_float(yh << 16));
+}
+
+__global__ void __launch_bounds__(kTileThreads) fwd_tile_kernel(const TileArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    bf16_t* rel_s = reinterpret_cast<bf16_t*>(smem);                                   // [cid_pad][kRelStride]
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int g = lane >> 4, j = lane & 15;
+    float* bias_s = reinterpret_cast<float*>(smem + (size_t)a.cid_pad * kRelStride * sizeof(bf16_t)) +
+                    (size_t)wave * 16 * a.bias_stride;                                  // [16 tokens][bias_stride]
+    bf16_t* v_s = reinterpret_cast<bf16_t*>(smem + (size_t)a.cid_pad * kRelStride * sizeof(bf16_t) +
+                                            (size_t)kTileWaves * 16 * a.bias_stride * sizeof(float)) +
+                  (size_t)wave * 32 * kVStride;                                         // [32 columns][kVStride]
+    // compact relative-position table, zero rows as padding
+    for (int i = threadIdx.x; i < a.cid_pad * 8; i += blockDim.x) {
+        const int cid = i >> 3, c8 = (i & 7) * 8;
+        uint4 w = make_uint4(0u, 0u, 0u, 0u);
+        if (cid < a.num_cids) w = *reinterpret_cast<const uint4*>(a.rel + (int64_t)a.cid_to_id[cid] * kD + c8);
+        *reinterpret_cast<uint4*>(rel_s + cid * kRelStride + c8) = w;
+    }
+    __syncthreads();
+
+    const float qscale = a.scale * kLog2e;
+    const int groups_per_bh = (a.num_tiles + kTileWaves - 1) / kTileWaves;
+    for (TileWalk w(a.BH * groups_per_bh); w.t < w.t_end; w.t += w.step) {
+        const int bh = w.t / groups_per_bh;
+        const int tile = (w.t - bh * groups_per_bh) * kTileWaves + wave;
+        if (tile >= a.num_tiles) continue;
+        const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
+        const rsrc_t rK = make_rsrc(a.K + base, a.slab_bytes), rV = make_rsrc(a.V + base, a.slab_bytes);
+        const int t0 = tile * 16;
+        const int cp0 = a.chunk_ptr[tile], nch = a.chunk_ptr[tile + 1] - cp0;
+        const int feat_off = 16 * g * (int)sizeof(bf16_t);  // this lane group's 16 features, in bytes
+
+        // Q^T operand: token j, features 16g..16g+15
+        const bf16_t* qrow = a.Q + base + (int64_t)(t0 + j) * a.sn + 16 * g;
+        const bf16x8_t qb0 = *reinterpret_cast<const bf16x8_t*>(qrow);
+        const bf16x8_t qb1 = *reinterpret_cast<const bf16x8_t*>(qrow + 8);
+
+        // bias^T = Rel x Q^T, kept in LDS as [token][compact id]
+        for (int c = 0; c < a.cid_pad; c += 16) {
+            const bf16_t* rrow = rel_s + (c + j) * kRelStride + 16 * g;
+            f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(rrow), qb0, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(rrow + 8), qb1, acc, 0, 0, 0);
+            *reinterpret_cast<f32x4_t*>(bias_s + j * a.bias_stride + c + 4 * g) = acc;
+        }
+        wave_lds_sync();
+
+        float m_run = kNegBig, l_part = 0.f;
+        f32x4_t o[4];
+#pragma unroll
+        for (int f = 0; f < 4; ++f) o[f] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+        for (int grp = 0; grp < nch; grp += kGroup) {
+            // scores of up to 8 chunks
+            float sc[kGroup][4];
+            Row<bf16_t> ka[kGroup], kb[kGroup];
+            uint2 mp[kGroup];
+#pragma unroll
+            for (int ci = 0; ci < kGroup; ++ci)
+                if (grp + ci < nch) {
+                    const int at = (cp0 + grp + ci) * 16 + j;
+                    const int node = a.cols[at];
+                    const int off = (int)__umul24(node, a.row_bytes) + feat_off;
+                    buf_row(rK, off, ka[ci]);
+                    buf_row(rK, off + 16, kb[ci]);
+                    mp[ci] = *reinterpret_cast<const uint2*>(a.map + (int64_t)at * 16 + 4 * g);
+                }
+            float gm = kNegBig;
+#pragma unroll
+            for (int ci = 0; ci < kGroup; ++ci) {
+                if (grp + ci < nch) {
+                    f32x4_t s4 = {0.f, 0.f, 0.f, 0.f};
+                    s4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ka[ci]), qb0, s4, 0, 0, 0);
+                    s4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kb[ci]), qb1, s4, 0, 0, 0);
+                    const int cid[4] = {(int)(short)(mp[ci].x & 0xFFFFu), (int)(short)(mp[ci].x >> 16),
+                                        (int)(short)(mp[ci].y & 0xFFFFu), (int)(short)(mp[ci].y >> 16)};
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const float b = bias_s[j * a.bias_stride + max(cid[r], 0)];
+                        sc[ci][r] = cid[r] >= 0 ? (s4[r] + b) * qscale : kNegBig;
+                        gm = fmaxf(gm, sc[ci][r]);
+                    }
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) sc[ci][r] = kNegBig;
+                }
+            }
+            gm = fmaxf(gm, __shfl_xor(gm, 16));
+            gm = fmaxf(gm, __shfl_xor(gm, 32));
+            const float mn = fmaxf(m_run, gm);
+            const float corr = fast_exp2(m_run - mn);
+            m_run = mn;
+            float psum = 0.f;
+#pragma unroll
+            for (int ci = 0; ci < kGroup; ++ci)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float p = sc[ci][r] > 0.5f * kNegBig ? fast_exp2(sc[ci][r] - mn) : 0.f;
+                    sc[ci][r] = p;
+                    psum += p;
+                }
+            l_part = l_part * corr + psum;
+            // the accumulators hold tokens 4g..4g+3: fetch their correction factors
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float cr = __shfl(corr, 4 * g + r);
+#pragma unroll
+                for (int f = 0; f < 4; ++f) o[f][r] *= cr;
+            }
+            // out += P V, two chunks (32 columns) at a time
+#pragma unroll
+            for (int pi = 0; pi < kGroup / 2; ++pi) {
+                if (grp + 2 * pi < nch) {
+                    const int at = (cp0 + grp + 2 * pi) * 16 + j;
+                    const int n0 = a.cols[at], n1 = a.cols[at + 16];
+                    Row<bf16_t> v00, v01, v10, v11;
+                    const int off0 = (int)__umul24(n0, a.row_bytes) + feat_off;
+                    const int off1 = (int)__umul24(n1, a.row_bytes) + feat_off;
+                    buf_row(rV, off0, v00);
+                    buf_row(rV, off0 + 16, v01);
+                    buf_row(rV, off1, v10);
+                    buf_row(rV, off1 + 16, v11);
+                    wave_lds_sync();  // the previous pair's reads of v_s are done
+                    uint2* d0 = reinterpret_cast<uint2*>(v_s + j * kVStride + 16 * g);
+                    uint2* d1 = reinterpret_cast<uint2*>(v_s + (16 + j) * kVStride + 16 * g);
+                    d0[0] = make_uint2(v00.w.x, v00.w.y);
+                    d0[1] = make_uint2(v00.w.z, v00.w.w);
+                    d0[2] = make_uint2(v01.w.x, v01.w.y);
+                    d0[3] = make_uint2(v01.w.z, v01.w.w);
+                    d1[0] = make_uint2(v10.w.x, v10.w.y);
+                    d1[1] = make_uint2(v10.w.z, v10.w.w);
+                    d1[2] = make_uint2(v11.w.x, v11.w.y);
+                    d1[3] = make_uint2(v11.w.z, v11.w.w);
+                    wave_lds_sync();
+                    u32x4 pa;
+                    pa.x = pack_bf16(sc[2 * pi][0], sc[2 * pi][1]);
+                    pa.y = pack_bf16(sc[2 * pi][2], sc[2 * pi][3]);
+                    pa.z = pack_bf16(sc[2 * pi + 1][0], sc[2 * pi + 1][1]);
+                    pa.w = pack_bf16(sc[2 * pi + 1][2], sc[2 * pi + 1][3]);
+                    const bf16x8_t pA = __builtin_bit_cast(bf16x8_t, pa);
+#pragma unroll
+                    for (int f = 0; f < 4; ++f) {
+                        // B[k][n]: column k of the pair (same interleaving as P), feature 16f + j
+                        const bf16_t* vc = v_s + 16 * f + j;
+                        u32x4 vb;
+                        vb.x = (uint32_t)vc[(4 * g + 0) * kVStride] | ((uint32_t)vc[(4 * g + 1) * kVStride] << 16);
+                        vb.y = (uint32_t)vc[(4 * g + 2) * kVStride] | ((uint32_t)vc[(4 * g + 3) * kVStride] << 16);
+                        vb.z = (uint32_t)vc[(16 + 4 * g + 0) * kVStride] | ((uint32_t)vc[(16 + 4 * g + 1) * kVStride] << 16);
+                        vb.w = (uint32_t)vc[(16 + 4 * g + 2) * kVStride] | ((uint32_t)vc[(16 + 4 * g + 3) * kVStride] << 16);
+                        o[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pA, __builtin_bit_cast(bf16x8_t, vb), o[f], 0, 0, 0);
+                    }
+                }
+            }
+        }
+        // row sums: token j is spread over the 4 lane groups
+        float l = l_part + __shfl_xor(l_part, 16);
+        l += __shfl_xor(l, 32);
+        if (g == 0) a.lse[(int64_t)bh * a.N + t0 + j] = (m_run + fast_log2(l)) * kLn2;
+        bf16_t* orow = a.out + base + (int64_t)t0 * a.sn + 16 * 0 + j;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float inv = 1.f / __shfl(l, 4 * g + r);
+#pragma unroll
+            for (int f = 0; f < 4; ++f)
+                orow[(int64_t)(4 * g + r) * a.sn + 16 * f] = (bf16_t)to_bf16_bits(o[f][r] * inv);
+        }
+        wave_lds_sync();  // bias_s and v_s are reused by the next tile
+    }
+}
+
+
+// ---- backward, query side, over the same dense tiles (bf16) --------------------------
+// Per tile: S^T and dP^T = V_chunk x dO^T on the matrix cores, p = exp2(s - lse),
+// w = p dP, delta = sum w; then, with K staged in LDS as the B operand,
+//   dQ_K = scale * (W K_U - delta * P K_U)       (the key part of dQ; lse is known, so
+// no online softmax and no second pass).  (w, p) of every edge goes to `wp` in CSR
+// order for the d_rel kernel, which also adds the relative-position part of dQ.
+__global__ void __launch_bounds__(kTileThreads) bwd_q_tile_kernel(const TileArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    bf16_t* rel_s = reinterpret_cast<bf16_t*>(smem);
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int g = lane >> 4, j = lane & 15;
+    float* bias_s = reinterpret_cast<float*>(smem + (size_t)a.cid_pad * kRelStride * sizeof(bf16_t)) +
+                    (size_t)wave * 16 * a.bias_stride;
+    bf16_t* k_s = reinterpret_cast<bf16_t*>(smem + (size_t)a.cid_pad * kRelStride * sizeof(bf16_t) +
+                                            (size_t)kTileWaves * 16 * a.bias_stride * sizeof(float)) +
+                  (size_t)wave * 32 * kVStride;
+    for (int i = threadIdx.x; i < a.cid_pad * 8; i += blockDim.x) {
+        const int cid = i >> 3, c8 = (i & 7) * 8;
+        uint4 w = make_uint4(0u, 0u, 0u, 0u);
+        if (cid < a.num_cids) w = *reinterpret_cast<const uint4*>(a.rel + (int64_t)a.cid_to_id[cid] * kD + c8);
+        *reinterpret_cast<uint4*>(rel_s + cid * kRelStride + c8) = w;
+    }
+    __syncthreads();
+
+    const float qscale = a.scale * kLog2e;
+    const int groups_per_bh = (a.num_tiles + kTileWaves - 1) / kTileWaves;
+    for (TileWalk w(a.BH * groups_per_bh); w.t < w.t_end; w.t += w.step) {
+        const int bh = w.t / groups_per_bh;
+        const int tile = (w.t - bh * groups_per_bh) * kTileWaves + wave;
+        if (tile >= a.num_tiles) continue;
+        const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
+        const rsrc_t rK = make_rsrc(a.K + base, a.slab_bytes), rV = make_rsrc(a.V + base, a.slab_bytes);
+        const int t0 = tile * 16;
+        const int cp0 = a.chunk_ptr[tile], nch = a.chunk_ptr[tile + 1] - cp0;
+        const int feat_off = 16 * g * (int)sizeof(bf16_t);
+
+        const bf16_t* qrow = a.Q + base + (int64_t)(t0 + j) * a.sn + 16 * g;
+        const bf16_t* grow = a.dout + base + (int64_t)(t0 + j) * a.sn + 16 * g;
+        const bf16x8_t qb0 = *reinterpret_cast<const bf16x8_t*>(qrow);
+        const bf16x8_t qb1 = *reinterpret_cast<const bf16x8_t*>(qrow + 8);
+        const bf16x8_t gb0 = *reinterpret_cast<const bf16x8_t*>(grow);
+        const bf16x8_t gb1 = *reinterpret_cast<const bf16x8_t*>(grow + 8);
+        const float lse2 = a.lse_r[(int64_t)bh * a.N + t0 + j] * kLog2e;
+        float2* wp_row = a.wp + (int64_t)bh * a.e_tok + a.row_ptr[t0 + j];
+
+        for (int c = 0; c < a.cid_pad; c += 16) {
+            const bf16_t* rrow = rel_s + (c + j) * kRelStride + 16 * g;
+            f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(rrow), qb0, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(rrow + 8), qb1, acc, 0, 0, 0);
+            *reinterpret_cast<f32x4_t*>(bias_s + j * a.bias_stride + c + 4 * g) = acc;
+        }
+        wave_lds_sync();
+
+        float dl_part = 0.f;
+        f32x4_t ow[4], op[4];
+#pragma unroll
+        for (int f = 0; f < 4; ++f) ow[f] = op[f] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+        for (int c2 = 0; c2 < nch; c2 += 2) {
+            float pw[2][4], pp[2][4];
+            Row<bf16_t> ka[2], kb[2], va[2], vb[2];
+            uint2 mp[2], ep[2];
+#pragma unroll
+            for (int ci = 0; ci < 2; ++ci) {
+                const int at = (cp0 + c2 + ci) * 16 + j;
+                const int off = (int)__umul24(a.cols[at], a.row_bytes) + feat_off;
+                buf_row(rK, off, ka[ci]);
+                buf_row(rK, off + 16, kb[ci]);
+                buf_row(rV, off, va[ci]);
+                buf_row(rV, off + 16, vb[ci]);
+                mp[ci] = *reinterpret_cast<const uint2*>(a.map + (int64_t)at * 16 + 4 * g);
+                ep[ci] = *reinterpret_cast<const uint2*>(a.emap + (int64_t)at * 16 + 4 * g);
+            }
+            wave_lds_sync();  // the previous pair's reads of k_s are done
+#pragma unroll
+            for (int ci = 0; ci < 2; ++ci) {
+                f32x4_t s4 = {0.f, 0.f, 0.f, 0.f}, d4 = {0.f, 0.f, 0.f, 0.f};
+                s4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ka[ci]), qb0, s4, 0, 0, 0);
+                s4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kb[ci]), qb1, s4, 0, 0, 0);
+                d4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(va[ci]), gb0, d4, 0, 0, 0);
+                d4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vb[ci]), gb1, d4, 0, 0, 0);
+                const int cid[4] = {(int)(short)(mp[ci].x & 0xFFFFu), (int)(short)(mp[ci].x >> 16),
+                                    (int)(short)(mp[ci].y & 0xFFFFu), (int)(short)(mp[ci].y >> 16)};
+                const int eo[4] = {(int)(ep[ci].x & 0xFFFFu), (int)(ep[ci].x >> 16), (int)(ep[ci].y & 0xFFFFu),
+                                   (int)(ep[ci].y >> 16)};
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const bool valid = cid[r] >= 0;
+                    const float b = bias_s[j * a.bias_stride + max(cid[r], 0)];
+                    const float p = valid ? fast_exp2((s4[r] + b) * qscale - lse2) : 0.f;
+                    const float wgt = p * d4[r];
+                    dl_part += wgt;
+                    pw[ci][r] = wgt;
+                    pp[ci][r] = p;
+                    if (valid) wp_row[eo[r]] = make_float2(wgt, p);
+                }
+                // stage the chunk's K rows as the B operand of the second product
+                uint2* d = reinterpret_cast<uint2*>(k_s + (16 * ci + j) * kVStride + 16 * g);
+                d[0] = make_uint2(ka[ci].w.x, ka[ci].w.y);
+                d[1] = make_uint2(ka[ci].w.z, ka[ci].w.w);
+                d[2] = make_uint2(kb[ci].w.x, kb[ci].w.y);
+                d[3] = make_uint2(kb[ci].w.z, kb[ci].w.w);
+            }
+            wave_lds_sync();
+            // W and P as A operands, each split into bf16 hi + lo: A - delta*Bv cancels when a
+            // row's softmax is peaked, so the two products need more than 8 mantissa bits
+            uint32_t whi[4], wlo[4], phi[4], plo[4];
+#pragma unroll
+            for (int ci = 0; ci < 2; ++ci) {
+                split_pack(pw[ci][0], pw[ci][1], whi[2 * ci], wlo[2 * ci]);
+                split_pack(pw[ci][2], pw[ci][3], whi[2 * ci + 1], wlo[2 * ci + 1]);
+                split_pack(pp[ci][0], pp[ci][1], phi[2 * ci], plo[2 * ci]);
+                split_pack(pp[ci][2], pp[ci][3], phi[2 * ci + 1], plo[2 * ci + 1]);
+            }
+            const u32x4 wh = {whi[0], whi[1], whi[2], whi[3]}, wl = {wlo[0], wlo[1], wlo[2], wlo[3]};
+            const u32x4 ph = {phi[0], phi[1], phi[2], phi[3]}, pl = {plo[0], plo[1], plo[2], plo[3]};
+            const bf16x8_t wH = __builtin_bit_cast(bf16x8_t, wh), wL = __builtin_bit_cast(bf16x8_t, wl);
+            const bf16x8_t pH = __builtin_bit_cast(bf16x8_t, ph), pL = __builtin_bit_cast(bf16x8_t, pl);
+#pragma unroll
+            for (int f = 0; f < 4; ++f) {
+                const bf16_t* kc = k_s + 16 * f + j;
+                u32x4 kt;
+                kt.x = (uint32_t)kc[(4 * g + 0) * kVStride] | ((uint32_t)kc[(4 * g + 1) * kVStride] << 16);
+                kt.y = (uint32_t)kc[(4 * g + 2) * kVStride] | ((uint32_t)kc[(4 * g + 3) * kVStride] << 16);
+                kt.z = (uint32_t)kc[(16 + 4 * g + 0) * kVStride] | ((uint32_t)kc[(16 + 4 * g + 1) * kVStride] << 16);
+                kt.w = (uint32_t)kc[(16 + 4 * g + 2) * kVStride] | ((uint32_t)kc[(16 + 4 * g + 3) * kVStride] << 16);
+                const bf16x8_t kB = __builtin_bit_cast(bf16x8_t, kt);
+                ow[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wH, kB, ow[f], 0, 0, 0);
+                ow[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wL, kB, ow[f], 0, 0, 0);
+                op[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pH, kB, op[f], 0, 0, 0);
+                op[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pL, kB, op[f], 0, 0, 0);
+            }
+        }
+        float delta = dl_part + __shfl_xor(dl_part, 16);
+        delta += __shfl_xor(delta, 32);
+        if (g == 0) a.stat[(int64_t)bh * a.N + t0 + j] = make_float2(lse2, delta);
+        float* qrow_out = a.dQ + base + (int64_t)t0 * a.sn + j;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float dr = __shfl(delta, 4 * g + r);
+#pragma unroll
+            for (int f = 0; f < 4; ++f)
+                qrow_out[(int64_t)(4 * g + r) * a.sn + 16 * f] = a.scale * (ow[f][r] - dr * op[f][r]);
+        }
+        wave_lds_sync();
     }
 }
 
@@ -969,11 +1389,94 @@ void use_schedule(AttnArgs& a, const Schedule& sc) {
     a.num_part = sc.num_part;
 }
 
+// LDS of fwd_tile_kernel for this graph, or 0 if the tile path does not apply
+size_t tile_lds_bytes(const bpt_graph* g, int* cid_pad, int* bias_stride) {
+    if (g->tiles.num_tiles == 0) return 0;
+    *cid_pad = (g->tiles.num_cids + 15) & ~15;
+    *bias_stride = *cid_pad + ((4 - *cid_pad % 32) + 32) % 32;  // = 4 mod 32: the 16 token rows hit different banks
+    return (size_t)*cid_pad * kRelStride * sizeof(bf16_t) + (size_t)kTileWaves * 16 * *bias_stride * sizeof(float) +
+           (size_t)kTileWaves * 32 * kVStride * sizeof(bf16_t);
+}
+
+void fill_tile_args(TileArgs& t, const bpt_graph* g, const AttnArgs& a, int cid_pad, int bias_stride);
+
+template <typename K>
+int launch_tiles(K kernel, const TileArgs& t, const DeviceLimits& lim, size_t lds, hipStream_t st) {
+    if (lds > 65536)
+        BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)lds));
+    int per_cu = 0;
+    BPT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kTileThreads, lds));
+    const int grid = std::max(8, lim.cus * std::max(1, per_cu) / 8 * 8);
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(kTileThreads), lds, st, t);
+    BPT_HIP(hipGetLastError());
+    return BPT_OK;
+}
+
+// bf16 backward, query side of the token rows on dense tiles
+int run_bwd_q_tiles(const bpt_graph* g, const AttnArgs& a, const DeviceLimits& lim, hipStream_t st) {
+    int cid_pad = 0, bias_stride = 0;
+    const size_t lds = tile_lds_bytes(g, &cid_pad, &bias_stride);
+    TileArgs t = {};
+    fill_tile_args(t, g, a, cid_pad, bias_stride);
+    return launch_tiles(bwd_q_tile_kernel, t, lim, lds, st);
+}
+
+void fill_tile_args(TileArgs& t, const bpt_graph* g, const AttnArgs& a, int cid_pad, int bias_stride) {
+    t.dout = static_cast<const bf16_t*>(a.dout);
+    t.lse_r = a.lse_r;
+    t.dQ = a.dQ;
+    t.stat = a.stat;
+    t.wp = a.wp;
+    t.e_tok = a.e_tok;
+    t.emap = g->tiles.emap;
+    t.row_ptr = g->row_ptr;
+    t.Q = static_cast<const bf16_t*>(a.Q);
+    t.K = static_cast<const bf16_t*>(a.K);
+    t.V = static_cast<const bf16_t*>(a.V);
+    t.rel = static_cast<const bf16_t*>(a.rel);
+    t.out = static_cast<bf16_t*>(a.out);
+    t.lse = a.lse_w;
+    t.sb = a.sb;
+    t.sh = a.sh;
+    t.sn = a.sn;
+    t.BH = a.BH;
+    t.H = a.H;
+    t.N = a.N;
+    t.scale = a.scale;
+    t.chunk_ptr = g->tiles.chunk_ptr;
+    t.cols = g->tiles.cols;
+    t.cid_to_id = g->tiles.cid_to_id;
+    t.map = g->tiles.map;
+    t.num_tiles = g->tiles.num_tiles;
+    t.num_cids = g->tiles.num_cids;
+    t.cid_pad = cid_pad;
+    t.bias_stride = bias_stride;
+    t.row_bytes = a.row_bytes;
+    t.slab_bytes = a.slab_bytes;
+}
+
+// bf16 forward: token rows as dense tiles on the matrix cores, span rows with the gather kernel
+int run_fwd_tiles(const bpt_graph* g, AttnArgs& a, const DeviceLimits& lim, size_t lds, int cid_pad, int bias_stride,
+                  hipStream_t st) {
+    TileArgs t = {};
+    fill_tile_args(t, g, a, cid_pad, bias_stride);
+    return launch_tiles(fwd_tile_kernel, t, lim, lds, st);
+}
+
 template <typename T>
 int run_fwd(const bpt_graph* g, AttnArgs& a, hipStream_t st) {
     DeviceLimits lim;
     int rc = device_limits(g, &lim);
     if (rc) return rc;
+    if (sizeof(T) == 2) {
+        int cid_pad = 0, bias_stride = 0;
+        const size_t tlds = tile_lds_bytes(g, &cid_pad, &bias_stride);
+        if (tlds > 0 && tlds <= lim.lds) {
+            if ((rc = run_fwd_tiles(g, a, lim, tlds, cid_pad, bias_stride, st))) return rc;
+            use_schedule(a, g->fwd_span);  // the gather kernel below only sees span rows
+        }
+    }
     const int ctx_rows = g->ctx_levels * g->rel_width;
     const size_t rel_b = (size_t)ctx_rows * kD * sizeof(T);
     const bool rel_lds = rel_b <= lim.lds;
@@ -988,10 +1491,11 @@ int run_fwd(const bpt_graph* g, AttnArgs& a, hipStream_t st) {
         rc = launch(fwd_kernel<T, false>, grid, kThreads, 0, st, a);
     }
     if (rc) return rc;
-    if (g->fwd.num_multi > 0) {
-        const int items = a.BH * g->fwd.num_multi;
-        hipLaunchKernelGGL(fwd_merge_kernel<T>, dim3((items + 3) / 4), dim3(256), 0, st, a, g->fwd.multi_row,
-                           g->fwd.multi_ptr, g->fwd.num_multi);
+    const Schedule& sc = a.seg_row == g->fwd_span.seg_row ? g->fwd_span : g->fwd;
+    if (sc.num_multi > 0) {
+        const int items = a.BH * sc.num_multi;
+        hipLaunchKernelGGL(fwd_merge_kernel<T>, dim3((items + 3) / 4), dim3(256), 0, st, a, sc.multi_row, sc.multi_ptr,
+                           sc.num_multi);
         BPT_HIP(hipGetLastError());
     }
     return BPT_OK;
@@ -1001,6 +1505,7 @@ int run_fwd(const bpt_graph* g, AttnArgs& a, hipStream_t st) {
 struct BwdPlan {
     int drel_rows = 0;        // d_rel rows token rows can touch
     bool drel_mfma = false;   // bf16 tensors: rel_grad_mfma_kernel; fp32: rel_grad_kernel
+    bool q_tiles = false;     // query side of token rows on dense tiles (bwd_q_tile_kernel)
     int drel_ipw = 32;        // ids per wavefront: 8, 16 or 32
     int drel_block = 32;      // token rows per block
     int drel_grid_x = 8, drel_grid_y = 1;
@@ -1016,8 +1521,15 @@ int plan_bwd(const bpt_graph* g, const bpt_shape_t* s, BwdPlan* p) {
     int64_t blocks;
     if (s->dtype == BPT_BF16) {  // matrix-core kernel
         p->drel_mfma = true;
-        const int nids = std::min(kRgIds, (p->drel_rows + 15) & ~15);
+        const int nids = std::min(kRgIds, (p->drel_rows + 31) & ~31);
         p->drel_lds = ((size_t)2 * nids + kD) * kRgStride * sizeof(bf16_t);
+        // dense tiles for the query side: only when one workgroup of the d_rel kernel sees all ids
+        int cid_pad = 0, bias_stride = 0;
+        const size_t tlds = tile_lds_bytes(g, &cid_pad, &bias_stride);
+        if (tlds > 0 && tlds <= lim.lds && p->drel_rows <= kRgIds) {
+            p->q_tiles = true;
+            p->drel_lds += (size_t)kD * (nids + 8) * sizeof(bf16_t);  // Rel^T
+        }
         p->drel_grid_y = (p->drel_rows + kRgIds - 1) / kRgIds;
         blocks = (int64_t)s->B * s->H * ((g->n + kRgRows - 1) / kRgRows);
     } else {
@@ -1037,7 +1549,7 @@ int plan_bwd(const bpt_graph* g, const bpt_shape_t* s, BwdPlan* p) {
     p->off_wp = off;
     off += align_up(bh * (size_t)g->num_token_edges * sizeof(float2));
     p->off_qpart = off;
-    off += align_up(bh * g->fwd.num_part * kQPartStride * sizeof(float));
+    off += align_up(bh * std::max(g->fwd.num_part, g->fwd_span.num_part) * kQPartStride * sizeof(float));
     p->off_kvpart = off;
     off += align_up(bh * g->tr.num_part * 2 * kD * sizeof(float));
     p->off_drel = off;
@@ -1073,6 +1585,12 @@ int run_bwd_q(const bpt_graph* g, const BwdPlan& p, AttnArgs& a, hipStream_t st)
     a.rel_rows_lds = rel_lds ? ctx_rows : 0;
     a.drel_rows = p.drel_rows;
     a.drel_block = p.drel_block;
+    const Schedule* sc = &g->fwd;
+    if (p.q_tiles) {  // token rows on the matrix cores; the gather kernel below only sees span rows
+        if ((rc = run_bwd_q_tiles(g, a, lim, st))) return rc;
+        use_schedule(a, g->fwd_span);
+        sc = &g->fwd_span;
+    }
     int grid = 8;
     if (rel_lds) {
         if ((rc = persistent_grid(bwd_q_kernel<T, true>, kThreads, rel_b, lim, &grid))) return rc;
@@ -1082,14 +1600,22 @@ int run_bwd_q(const bpt_graph* g, const BwdPlan& p, AttnArgs& a, hipStream_t st)
         rc = launch(bwd_q_kernel<T, false>, grid, kThreads, 0, st, a);
     }
     if (rc) return rc;
-    if (g->fwd.num_multi > 0) {
-        const int items = a.BH * g->fwd.num_multi;
-        hipLaunchKernelGGL(bwd_q_merge_kernel, dim3((items + 3) / 4), dim3(256), 0, st, a, g->fwd.multi_row,
-                           g->fwd.multi_ptr, g->fwd.num_multi);
+    if (sc->num_multi > 0) {
+        const int items = a.BH * sc->num_multi;
+        hipLaunchKernelGGL(bwd_q_merge_kernel, dim3((items + 3) / 4), dim3(256), 0, st, a, sc->multi_row,
+                           sc->multi_ptr, sc->num_multi);
         BPT_HIP(hipGetLastError());
     }
     if (p.drel_mfma) {
-        hipLaunchKernelGGL(rel_grad_mfma_kernel, dim3(p.drel_grid_x, p.drel_grid_y), dim3(kThreads), p.drel_lds, st, a);
+        if (p.drel_lds > 65536)
+            BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rel_grad_mfma_kernel<true>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.drel_lds));
+        if (p.q_tiles)
+            hipLaunchKernelGGL(rel_grad_mfma_kernel<true>, dim3(p.drel_grid_x, p.drel_grid_y), dim3(kThreads),
+                               p.drel_lds, st, a);
+        else
+            hipLaunchKernelGGL(rel_grad_mfma_kernel<false>, dim3(p.drel_grid_x, p.drel_grid_y), dim3(kThreads),
+                               p.drel_lds, st, a);
         BPT_HIP(hipGetLastError());
         rc = BPT_OK;
     } else {
@@ -1187,7 +1713,8 @@ extern "C" {
 
 size_t bpt_attn_fwd_workspace(const bpt_graph_t* g, const bpt_shape_t* s) {
     if (bpt::check_shape(g, s) != BPT_OK) return 0;
-    return bpt::align_up((size_t)s->B * s->H * g->fwd.num_part * bpt::kPartStride * sizeof(float));
+    return bpt::align_up((size_t)s->B * s->H * std::max(g->fwd.num_part, g->fwd_span.num_part) * bpt::kPartStride *
+                         sizeof(float));
 }
 
 size_t bpt_attn_bwd_workspace(const bpt_graph_t* g, const bpt_shape_t* s) {

@@ -367,7 +367,7 @@ int upload(const std::vector<T>& h, T** d) {
 // Cut rows into segments of at most kSeg edges and group consecutive segments
 // into tiles of about kTileWork work units.  Rows without edges still get one
 // (empty) segment so that their outputs are written.
-int make_schedule(const std::vector<int32_t>& ptr, Schedule& out) {
+int make_schedule(const std::vector<int32_t>& ptr, int32_t first_row, Schedule& out) {
     const int32_t rows = (int32_t)ptr.size() - 1;
     std::vector<int32_t> seg_row, seg_begin, seg_part, tile_ptr, multi_row, multi_ptr;
     seg_row.reserve(rows + rows / 8);
@@ -377,7 +377,7 @@ int make_schedule(const std::vector<int32_t>& ptr, Schedule& out) {
     multi_ptr.push_back(0);
     int64_t work = 0;
     int32_t parts = 0;
-    for (int32_t u = 0; u < rows; ++u) {
+    for (int32_t u = first_row; u < rows; ++u) {
         const int32_t b = ptr[u], deg = ptr[u + 1] - b;
         const int32_t nseg = deg <= kSeg ? 1 : (deg + kSeg - 1) / kSeg;
         for (int32_t s = 0; s < nseg; ++s) {
@@ -406,6 +406,84 @@ int make_schedule(const std::vector<int32_t>& ptr, Schedule& out) {
         (rc = upload(seg_part, &out.seg_part)) || (rc = upload(tile_ptr, &out.tile_ptr)) ||
         (rc = upload(multi_row, &out.multi_row)) || (rc = upload(multi_ptr, &out.multi_ptr)))
         return rc;
+    return BPT_OK;
+}
+
+void free_tiles(TokenTiles& t) {
+    (void)hipFree(t.chunk_ptr);
+    (void)hipFree(t.cols);
+    (void)hipFree(t.map);
+    (void)hipFree(t.emap);
+    (void)hipFree(t.cid_to_id);
+    t = TokenTiles();
+}
+
+// Tile metadata for the matrix-core kernels, from the token rows of the CSR.  The
+// key nodes of 16 consecutive token rows are bucketed by (level, side); inside a
+// bucket the union is taken as the node range [min, max] (a node in the range that
+// no row attends to is just a masked column), so a column's slot follows from the
+// bucket's first slot and first node.  Buckets are laid out by level, left before
+// right, i.e. in ascending node id.
+int make_token_tiles(int32_t n, int32_t k, int32_t num_levels, const std::vector<int32_t>& ptr,
+                     const std::vector<int32_t>& col, const std::vector<int32_t>& rel, TokenTiles& out) {
+    const int32_t tiles = n / 16, W = 2 * (k + 1) + 1, zero = k + 1, num_ids = num_levels * W;
+    const int32_t nb = 2 * num_levels;  // bucket 0: level 0; 2l-1 / 2l: left / right of level l
+    std::vector<int32_t> cid(num_ids, -1), cid_to_id;
+    for (int32_t e = 0; e < ptr[n]; ++e) cid[rel[e]] = 0;
+    for (int32_t id = 0; id < num_ids; ++id)
+        if (cid[id] == 0) {
+            cid[id] = (int32_t)cid_to_id.size();
+            cid_to_id.push_back(id);
+        }
+    if (cid_to_id.size() > 32767) return BPT_OK;  // ids would not fit the 16-bit maps: no tile path
+    auto bucket_of = [&](int32_t r) {
+        const int32_t lev = r / W, ord = r % W - zero;
+        return lev == 0 ? 0 : 2 * lev - 1 + (ord > 0 ? 1 : 0);
+    };
+    std::vector<int32_t> chunk_ptr(1, 0), cols, lo(nb), hi(nb), first(nb);
+    std::vector<int16_t> map, emap;
+    for (int32_t t = 0; t < tiles; ++t) {
+        std::fill(lo.begin(), lo.end(), INT32_MAX);
+        std::fill(hi.begin(), hi.end(), -1);
+        const int32_t b = ptr[16 * t], e = ptr[16 * t + 16];
+        for (int32_t x = b; x < e; ++x) {
+            const int32_t q = bucket_of(rel[x]);
+            lo[q] = std::min(lo[q], col[x]);
+            hi[q] = std::max(hi[q], col[x]);
+        }
+        int32_t total = 0;
+        for (int32_t q = 0; q < nb; ++q) {
+            first[q] = total;
+            if (hi[q] >= 0) total += hi[q] - lo[q] + 1;
+        }
+        int32_t nch = (total + 15) / 16;
+        nch += nch & 1;  // even: the kernels consume chunks in pairs
+        const size_t c0 = cols.size(), m0 = map.size();
+        if ((m0 + (size_t)nch * 256) * sizeof(int16_t) > ((size_t)256 << 20)) return BPT_OK;  // too large: no tile path
+        cols.resize(c0 + (size_t)nch * 16, 16 * t);  // padding columns point at a real node and stay masked
+        for (int32_t q = 0; q < nb; ++q)
+            for (int32_t v = lo[q]; hi[q] >= 0 && v <= hi[q]; ++v) cols[c0 + first[q] + (v - lo[q])] = v;
+        map.resize(m0 + (size_t)nch * 256, (int16_t)-1);
+        emap.resize(m0 + (size_t)nch * 256, (int16_t)-1);
+        for (int32_t r = 0; r < 16; ++r) {
+            const int32_t rb = ptr[16 * t + r], re = ptr[16 * t + r + 1];
+            if (re - rb > 32767) return BPT_OK;  // edge offsets would not fit: no tile path
+            for (int32_t x = rb; x < re; ++x) {
+                const int32_t q = bucket_of(rel[x]);
+                const int32_t slot = first[q] + col[x] - lo[q];
+                const size_t at = m0 + ((size_t)(slot >> 4) * 16 + r) * 16 + (slot & 15);
+                map[at] = (int16_t)cid[rel[x]];
+                emap[at] = (int16_t)(x - rb);
+            }
+        }
+        chunk_ptr.push_back((int32_t)(cols.size() / 16));
+    }
+    out.num_cids = (int32_t)cid_to_id.size();
+    int rc;
+    if ((rc = upload(chunk_ptr, &out.chunk_ptr)) || (rc = upload(cols, &out.cols)) || (rc = upload(map, &out.map)) ||
+        (rc = upload(emap, &out.emap)) || (rc = upload(cid_to_id, &out.cid_to_id)))
+        return rc;
+    out.num_tiles = tiles;
     return BPT_OK;
 }
 
@@ -500,8 +578,16 @@ int build(int32_t n, int32_t k, int32_t causal, hipStream_t st, bpt_graph* g) {
     BPT_HIP(hipMemcpyAsync(h_ptr.data(), g->row_ptr, sizeof(int32_t) * h_ptr.size(), hipMemcpyDeviceToHost, st));
     BPT_HIP(hipMemcpyAsync(h_tptr.data(), g->t_ptr, sizeof(int32_t) * h_tptr.size(), hipMemcpyDeviceToHost, st));
     BPT_HIP(hipStreamSynchronize(st));
-    if ((rc = make_schedule(h_ptr, g->fwd))) return rc;
-    if ((rc = make_schedule(h_tptr, g->tr))) return rc;
+    if ((rc = make_schedule(h_ptr, 0, g->fwd))) return rc;
+    if ((rc = make_schedule(h_tptr, 0, g->tr))) return rc;
+    if (n >= 16 && e_tok < ((int64_t)1 << 27)) {  // dense token tiles for the matrix-core forward
+        std::vector<int32_t> h_col((size_t)e_tok), h_rel((size_t)e_tok);
+        BPT_HIP(hipMemcpyAsync(h_col.data(), g->col, sizeof(int32_t) * h_col.size(), hipMemcpyDeviceToHost, st));
+        BPT_HIP(hipMemcpyAsync(h_rel.data(), g->rel, sizeof(int32_t) * h_rel.size(), hipMemcpyDeviceToHost, st));
+        BPT_HIP(hipStreamSynchronize(st));
+        if ((rc = make_token_tiles(n, k, num_levels, h_ptr, h_col, h_rel, g->tiles))) return rc;
+        if (g->tiles.num_tiles > 0 && (rc = make_schedule(h_ptr, n, g->fwd_span))) return rc;
+    }
     return BPT_OK;
 }
 
@@ -521,6 +607,8 @@ void bpt_graph_destroy(bpt_graph_t* g) {
     (void)hipFree(g->t_rel);
     bpt::free_schedule(g->fwd);
     bpt::free_schedule(g->tr);
+    bpt::free_schedule(g->fwd_span);
+    bpt::free_tiles(g->tiles);
     delete g;
 }
 

@@ -28,6 +28,20 @@ struct Schedule {
     int32_t* multi_ptr = nullptr;  // [num_multi+1] their partial slots
 };
 
+// Dense tiles over the token rows, for the matrix-core forward.  A tile is 16
+// consecutive token rows; its columns are the union of the rows' key nodes in
+// ascending node id, cut into chunks of 16 (an even number of chunks per tile;
+// padding slots repeat a real node and are masked).
+struct TokenTiles {
+    int32_t num_tiles = 0;   // n / 16; 0 when the tile path is not built
+    int32_t num_cids = 0;    // relative-position ids used by token rows (compact numbering)
+    int32_t* chunk_ptr = nullptr;  // [num_tiles+1] first chunk of a tile
+    int32_t* cols = nullptr;       // [chunks][16] node id of a column
+    int16_t* map = nullptr;        // [chunks][16 rows][16 columns] compact id of the edge, or -1
+    int16_t* emap = nullptr;       // same shape: position of the edge in its CSR row, or -1
+    int32_t* cid_to_id = nullptr;  // [num_cids] compact id -> row of the relative-position table
+};
+
 }  // namespace bpt
 
 struct bpt_graph {
@@ -42,6 +56,8 @@ struct bpt_graph {
     // transposed adjacency by key node
     int32_t *t_ptr = nullptr, *t_src = nullptr, *t_eid = nullptr, *t_rel = nullptr;
     bpt::Schedule fwd, tr;
+    bpt::Schedule fwd_span;   // span rows only (used with the token tiles)
+    bpt::TokenTiles tiles;
 };
 
 #define BPT_HIP(expr)                                  \
