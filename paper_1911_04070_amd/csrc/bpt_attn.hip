@@ -198,6 +198,18 @@ __device__ __forceinline__ uint32_t to_bf16_bits(float f) {  // round to nearest
     uint32_t u = __float_as_uint(f);
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
+__device__ __forceinline__ void store8(float* p, const float (&x)[8]) {
+    *reinterpret_cast<float4*>(p) = make_float4(x[0], x[1], x[2], x[3]);
+    *reinterpret_cast<float4*>(p + 4) = make_float4(x[4], x[5], x[6], x[7]);
+}
+__device__ __forceinline__ void store8(bf16_t* p, const float (&x)[8]) {
+    uint4 w;
+    w.x = to_bf16_bits(x[0]) | (to_bf16_bits(x[1]) << 16);
+    w.y = to_bf16_bits(x[2]) | (to_bf16_bits(x[3]) << 16);
+    w.z = to_bf16_bits(x[4]) | (to_bf16_bits(x[5]) << 16);
+    w.w = to_bf16_bits(x[6]) | (to_bf16_bits(x[7]) << 16);
+    *reinterpret_cast<uint4*>(p) = w;
+}
 __device__ __forceinline__ void store1(float* p, float x) { *p = x; }
 __device__ __forceinline__ void store1(bf16_t* p, float x) { *p = (bf16_t)to_bf16_bits(x); }
 
@@ -320,6 +332,57 @@ __device__ __forceinline__ void fwd_segment(const AttnArgs& a, const T* rel_s, r
     }
 }
 
+// Eight consecutive span rows of one level (equal degree deg <= 64, keys = the deg
+// consecutive tokens each span contains), one row per 8-lane group: no neighbour
+// indices to fetch, no masking, and nothing to merge between the groups -- each
+// group finishes its own row.  Short span rows are most of the rows of the graph,
+// and one wavefront per row would spend its time in row set-up.
+template <typename T>
+__device__ __forceinline__ void fwd_span8(const AttnArgs& a, rsrc_t rK, rsrc_t rV, int bh, int64_t base, int u0, int e0,
+                                          int deg, int lane) {
+    const int slot = lane >> 3, sub = lane & 7;
+    const int lane_off = sub * 8 * (int)sizeof(T);
+    const int u = u0 + slot;
+    const int tok0 = a.ia[e0 + slot * deg];  // first token of this group's span
+    Row<T> k0 = gather_row<T>(rK, tok0, a.row_bytes, lane_off), v0 = gather_row<T>(rV, tok0, a.row_bytes, lane_off);
+    const Row<T> q = load_row(static_cast<const T*>(a.Q) + base + (int64_t)u * a.sn + sub * 8);
+    const float qscale = a.scale * kLog2e;
+    const float shift =
+        sum8(dot8(q, load_row(static_cast<const T*>(a.rel) + (int64_t)a.ib[e0] * kD + sub * 8), 0.f)) * qscale;
+    float m = kNegBig, l = 0.f, acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+    auto step = [&](int i, const Row<T>& kc, const Row<T>& vc, Row<T>& kn, Row<T>& vn) {
+        const int nxt = tok0 + min(i + 1, deg - 1);
+        kn = gather_row<T>(rK, nxt, a.row_bytes, lane_off);
+        vn = gather_row<T>(rV, nxt, a.row_bytes, lane_off);
+        const float sc = sum8(dot8(q, kc, 0.f)) * qscale + shift;
+        const bool up = sc > m;
+        const float e = fast_exp2(up ? m - sc : sc - m);
+        const float corr = up ? e : 1.f, p = up ? 1.f : e;
+        m = up ? sc : m;
+        float vv[8];
+        unpack(vc, vv);
+        l *= corr;
+        l += p;
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+            acc[x] *= corr;
+            acc[x] = fmaf(p, vv[x], acc[x]);
+        }
+    };
+    Row<T> k1, v1;
+    for (int i = 0; i < deg; i += 2) {  // deg is a power of two >= 2
+        step(i, k0, v0, k1, v1);
+        step(i + 1, k1, v1, k0, v0);
+    }
+    const float inv = 1.f / l;
+#pragma unroll
+    for (int x = 0; x < 8; ++x) acc[x] *= inv;
+    store8(static_cast<T*>(a.out) + base + (int64_t)u * a.sn + sub * 8, acc);
+    if (sub == 0) a.lse_w[(int64_t)bh * a.N + u] = (m + fast_log2(l)) * kLn2;
+}
+
 template <typename T, bool REL_LDS>
 __global__ void __launch_bounds__(kThreads) fwd_kernel(const AttnArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -344,7 +407,9 @@ __global__ void __launch_bounds__(kThreads) fwd_kernel(const AttnArgs a) {
             const int e1 = min(e0 + kSeg, a.ptr[u + 1]);
             const int part = a.seg_part[s];
             if (e1 <= e0) continue;  // no row of this adjacency is empty
-            if (u >= a.n_tokens)
+            if (part == kPartSpan8)
+                fwd_span8<T>(a, rK, rV, bh, base, u, e0, a.ptr[u + 1] - e0, lane);
+            else if (u >= a.n_tokens)
                 fwd_segment<T, REL_LDS, true>(a, rel_s, rK, rV, rIa, rIb, bh, base, u, e0, e1, part, lane);
             else
                 fwd_segment<T, REL_LDS, false>(a, rel_s, rK, rV, rIa, rIb, bh, base, u, e0, e1, part, lane);
@@ -480,6 +545,61 @@ __device__ __forceinline__ void bwd_q_segment(const AttnArgs& a, const T* rel_s,
     }
 }
 
+// Query side of eight consecutive short span rows, one row per 8-lane group (see fwd_span8).
+template <typename T>
+__device__ __forceinline__ void bwd_q_span8(const AttnArgs& a, rsrc_t rK, rsrc_t rV, int bh, int64_t base, int u0,
+                                            int e0, int deg, int lane) {
+    const int slot = lane >> 3, sub = lane & 7;
+    const int lane_off = sub * 8 * (int)sizeof(T);
+    const int u = u0 + slot;
+    const int tok0 = a.ia[e0 + slot * deg];
+    Row<T> k0 = gather_row<T>(rK, tok0, a.row_bytes, lane_off), v0 = gather_row<T>(rV, tok0, a.row_bytes, lane_off);
+    float qs[8];
+    load8(static_cast<const T*>(a.Q) + base + (int64_t)u * a.sn + sub * 8, qs);
+    const Row<T> g = load_row(static_cast<const T*>(a.dout) + base + (int64_t)u * a.sn + sub * 8);
+    const float qscale = a.scale * kLog2e;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) qs[i] *= qscale;
+    const float lse2 = a.lse_r[(int64_t)bh * a.N + u] * kLog2e;
+    float shift;
+    {
+        float r[8], d = 0.f;
+        load8(static_cast<const T*>(a.rel) + (int64_t)a.ib[e0] * kD + sub * 8, r);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) d += qs[i] * r[i];
+        shift = sum8(d);
+    }
+    float A[8], Bv[8], dl = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) A[i] = Bv[i] = 0.f;
+    auto step = [&](int i, const Row<T>& kc, const Row<T>& vc, Row<T>& kn, Row<T>& vn) {
+        const int nxt = tok0 + min(i + 1, deg - 1);
+        kn = gather_row<T>(rK, nxt, a.row_bytes, lane_off);
+        vn = gather_row<T>(rV, nxt, a.row_bytes, lane_off);
+        float kk[8], d = 0.f;
+        unpack(kc, kk);
+#pragma unroll
+        for (int x = 0; x < 8; ++x) d += qs[x] * kk[x];
+        const float p = fast_exp2(sum8(d) + shift - lse2);
+        const float wgt = p * sum8(dot8(g, vc, 0.f));
+        dl += wgt;
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+            A[x] = fmaf(wgt, kk[x], A[x]);
+            Bv[x] = fmaf(p, kk[x], Bv[x]);
+        }
+    };
+    Row<T> k1, v1;
+    for (int i = 0; i < deg; i += 2) {
+        step(i, k0, v0, k1, v1);
+        step(i + 1, k1, v1, k0, v0);
+    }
+#pragma unroll
+    for (int x = 0; x < 8; ++x) A[x] = a.scale * (A[x] - dl * Bv[x]);
+    store8(a.dQ + base + (int64_t)u * a.sn + sub * 8, A);
+    if (sub == 0) a.stat[(int64_t)bh * a.N + u] = make_float2(lse2, dl);
+}
+
 template <typename T, bool REL_LDS>
 __global__ void __launch_bounds__(kThreads) bwd_q_kernel(const AttnArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -504,7 +624,9 @@ __global__ void __launch_bounds__(kThreads) bwd_q_kernel(const AttnArgs a) {
             const int e1 = min(e0 + kSeg, a.ptr[u + 1]);
             const int part = a.seg_part[s];
             if (e1 <= e0) continue;
-            if (u >= a.n_tokens)
+            if (part == kPartSpan8)
+                bwd_q_span8<T>(a, rK, rV, bh, base, u, e0, a.ptr[u + 1] - e0, lane);
+            else if (u >= a.n_tokens)
                 bwd_q_segment<T, REL_LDS, true>(a, rel_s, rK, rV, rIa, rIb, bh, base, u, e0, e1, part, lane);
             else
                 bwd_q_segment<T, REL_LDS, false>(a, rel_s, rK, rV, rIa, rIb, bh, base, u, e0, e1, part, lane);

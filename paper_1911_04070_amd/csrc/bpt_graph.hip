@@ -367,7 +367,9 @@ int upload(const std::vector<T>& h, T** d) {
 // Cut rows into segments of at most kSeg edges and group consecutive segments
 // into tiles of about kTileWork work units.  Rows without edges still get one
 // (empty) segment so that their outputs are written.
-int make_schedule(const std::vector<int32_t>& ptr, int32_t first_row, Schedule& out) {
+// Rows from `span_from` on are span rows: 8 consecutive ones of equal degree <= kSpan8MaxDeg
+// become one segment marked kPartSpan8 (pass the row count to disable).
+int make_schedule(const std::vector<int32_t>& ptr, int32_t first_row, int32_t span_from, Schedule& out) {
     const int32_t rows = (int32_t)ptr.size() - 1;
     std::vector<int32_t> seg_row, seg_begin, seg_part, tile_ptr, multi_row, multi_ptr;
     seg_row.reserve(rows + rows / 8);
@@ -379,6 +381,22 @@ int make_schedule(const std::vector<int32_t>& ptr, int32_t first_row, Schedule& 
     int32_t parts = 0;
     for (int32_t u = first_row; u < rows; ++u) {
         const int32_t b = ptr[u], deg = ptr[u + 1] - b;
+        if (u >= span_from && u + 8 <= rows && deg >= 2 && deg <= kSpan8MaxDeg && ptr[u + 8] - b == 8 * deg) {
+            bool same = true;
+            for (int32_t x = 1; x < 8; ++x) same = same && ptr[u + x + 1] - ptr[u + x] == deg;
+            if (same) {
+                seg_row.push_back(u);
+                seg_begin.push_back(b);
+                seg_part.push_back(kPartSpan8);
+                work += 8 * deg + kRowCost;
+                if (work >= kTileWork) {
+                    tile_ptr.push_back((int32_t)seg_row.size());
+                    work = 0;
+                }
+                u += 7;
+                continue;
+            }
+        }
         const int32_t nseg = deg <= kSeg ? 1 : (deg + kSeg - 1) / kSeg;
         for (int32_t s = 0; s < nseg; ++s) {
             const int32_t len = std::min<int32_t>(kSeg, deg - s * kSeg);
@@ -578,15 +596,15 @@ int build(int32_t n, int32_t k, int32_t causal, hipStream_t st, bpt_graph* g) {
     BPT_HIP(hipMemcpyAsync(h_ptr.data(), g->row_ptr, sizeof(int32_t) * h_ptr.size(), hipMemcpyDeviceToHost, st));
     BPT_HIP(hipMemcpyAsync(h_tptr.data(), g->t_ptr, sizeof(int32_t) * h_tptr.size(), hipMemcpyDeviceToHost, st));
     BPT_HIP(hipStreamSynchronize(st));
-    if ((rc = make_schedule(h_ptr, 0, g->fwd))) return rc;
-    if ((rc = make_schedule(h_tptr, 0, g->tr))) return rc;
+    if ((rc = make_schedule(h_ptr, 0, n, g->fwd))) return rc;
+    if ((rc = make_schedule(h_tptr, 0, num_nodes, g->tr))) return rc;
     if (n >= 16 && e_tok < ((int64_t)1 << 27)) {  // dense token tiles for the matrix-core forward
         std::vector<int32_t> h_col((size_t)e_tok), h_rel((size_t)e_tok);
         BPT_HIP(hipMemcpyAsync(h_col.data(), g->col, sizeof(int32_t) * h_col.size(), hipMemcpyDeviceToHost, st));
         BPT_HIP(hipMemcpyAsync(h_rel.data(), g->rel, sizeof(int32_t) * h_rel.size(), hipMemcpyDeviceToHost, st));
         BPT_HIP(hipStreamSynchronize(st));
         if ((rc = make_token_tiles(n, k, num_levels, h_ptr, h_col, h_rel, g->tiles))) return rc;
-        if (g->tiles.num_tiles > 0 && (rc = make_schedule(h_ptr, n, g->fwd_span))) return rc;
+        if (g->tiles.num_tiles > 0 && (rc = make_schedule(h_ptr, n, n, g->fwd_span))) return rc;
     }
     return BPT_OK;
 }

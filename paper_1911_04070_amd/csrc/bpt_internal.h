@@ -12,6 +12,8 @@ constexpr int kD = 64;            // head width the kernels are written for
 constexpr int kSeg = 512;         // most edges one wavefront handles for one row
 constexpr int kTileWork = 4096;   // target work (edges + per-row cost) of one workgroup tile
 constexpr int kRowCost = 24;      // per-row overhead, in edge equivalents, for tile balancing
+constexpr int kPartSpan8 = -2;    // seg_part of a group of 8 equal-degree span rows handled one per 8-lane group
+constexpr int kSpan8MaxDeg = 64;
 constexpr int kPartStride = 66;   // forward partial: 64 accumulators, running max, running sum
 
 // A launch schedule over one adjacency (by query node, or transposed by key
@@ -22,7 +24,7 @@ struct Schedule {
     int32_t num_segs = 0, num_tiles = 0, num_multi = 0, num_part = 0;
     int32_t* seg_row = nullptr;    // [num_segs]   row (node id) of the segment
     int32_t* seg_begin = nullptr;  // [num_segs]   first edge of the segment
-    int32_t* seg_part = nullptr;   // [num_segs]   partial slot, or -1 if the row has one segment
+    int32_t* seg_part = nullptr;   // [num_segs]   partial slot, -1 if the row has one segment, kPartSpan8 for a row group
     int32_t* tile_ptr = nullptr;   // [num_tiles+1] segments of a tile
     int32_t* multi_row = nullptr;  // [num_multi]  rows that have several segments
     int32_t* multi_ptr = nullptr;  // [num_multi+1] their partial slots
