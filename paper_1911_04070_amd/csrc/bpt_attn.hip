@@ -1378,6 +1378,244 @@ __global__ void __launch_bounds__(kTileThreads) bwd_q_tile_kernel(const TileArgs
     }
 }
 
+
+// ---- backward, key side, over dense tiles of key nodes (bf16) --------------------------
+// A wavefront owns up to 16 consecutive key nodes of one level and walks (a slice of)
+// the nodes that attend to them, 32 at a time.  With the queries on the M side,
+//   S[query][key]  = Q_chunk (A, rows from memory) x K_tile^T (B, rows from memory),
+//   dP[query][key] = dO_chunk x V_tile^T,   bias[query][id] = Q_chunk x Rel_sel^T,
+// the result C[m][n] has key n = lane%16 and queries 4*(lane/16)..+3 in the registers,
+// which is the A-operand layout of the second products (contraction over queries):
+//   dK[key][f] += dS^T x Q_chunk,   dV[key][f] += P^T x dO_chunk
+// with Q and dO rows read transposed out of LDS.  lse and the exact delta of every
+// query come from the query side (`stat`), so dS is formed in fp32 before it is
+// rounded to bf16 for the product.  No atomics: a tile whose query list is cut into
+// several tasks is summed by kv_tile_merge_kernel in task order.
+constexpr int kMaxBiasChunks = 6;
+struct KeyArgs {
+    const bf16_t *Q, *K, *V, *rel, *dout;
+    const float2* stat;
+    float *dK, *dV, *part;
+    int64_t sb, sh, sn;
+    int32_t BH, H, N, num_levels;
+    float scale;
+    int32_t row_bytes;
+    uint32_t slab_bytes;
+    const int32_t *tile_node0, *tile_info, *cols, *task_tile, *task_c0, *task_nch, *task_part;
+    const int16_t* map;
+    int32_t num_tasks, num_part, nb_pad, W, zero;
+};
+
+__global__ void __launch_bounds__(kTileThreads) bwd_kv_tile_kernel(const KeyArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int g = lane >> 4, j = lane & 15;
+    const int bstride = a.nb_pad + 1;
+    float* bias_s = reinterpret_cast<float*>(smem) + (size_t)wave * 32 * bstride;               // [32 queries][ids]
+    bf16_t* q_s = reinterpret_cast<bf16_t*>(smem + (size_t)kTileWaves * 32 * bstride * sizeof(float)) +
+                  (size_t)wave * 64 * kVStride;                                                  // [32 queries][kVStride]
+    bf16_t* g_s = q_s + 32 * kVStride;
+    const float qscale = a.scale * kLog2e;
+    const int nbc = a.nb_pad >> 4;
+    const int groups = (a.num_tasks + kTileWaves - 1) / kTileWaves;
+
+    for (TileWalk w(a.BH * groups); w.t < w.t_end; w.t += w.step) {
+        const int bh = w.t / groups;
+        const int task = (w.t - bh * groups) * kTileWaves + wave;
+        if (task >= a.num_tasks) continue;
+        const int kt = a.task_tile[task], c0 = a.task_c0[task], nch = a.task_nch[task], part = a.task_part[task];
+        const int node0 = a.tile_node0[kt], info = a.tile_info[kt];
+        const int level = info & 255, nkeys = info >> 8;
+        const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
+        const rsrc_t rQ = make_rsrc(a.Q + base, a.slab_bytes), rG = make_rsrc(a.dout + base, a.slab_bytes);
+        const rsrc_t rS = make_rsrc(a.stat + (int64_t)bh * a.N, (uint32_t)a.N * 8u);
+        const int feat_off = 16 * g * (int)sizeof(bf16_t);
+
+        // B operands: the tile's keys (lane j <-> key j) and the rows of the table this level can meet
+        const int64_t krow = base + (int64_t)(node0 + min(j, nkeys - 1)) * a.sn + 16 * g;
+        const bf16x8_t kb0 = *reinterpret_cast<const bf16x8_t*>(a.K + krow);
+        const bf16x8_t kb1 = *reinterpret_cast<const bf16x8_t*>(a.K + krow + 8);
+        const bf16x8_t vb0 = *reinterpret_cast<const bf16x8_t*>(a.V + krow);
+        const bf16x8_t vb1 = *reinterpret_cast<const bf16x8_t*>(a.V + krow + 8);
+        bf16x8_t rb[kMaxBiasChunks][2];
+#pragma unroll
+        for (int bc = 0; bc < kMaxBiasChunks; ++bc)
+            if (bc < nbc) {
+                const int bid = 16 * bc + j;
+                int row = 0;
+                if (bid < a.W)
+                    row = level * a.W + bid;                        // (level, order)
+                else if (bid - a.W + 1 < a.num_levels)
+                    row = (bid - a.W + 1) * a.W + a.zero;            // r_anc of the ancestor's level
+                const bf16_t* rr = a.rel + (int64_t)row * kD + 16 * g;
+                rb[bc][0] = *reinterpret_cast<const bf16x8_t*>(rr);
+                rb[bc][1] = *reinterpret_cast<const bf16x8_t*>(rr + 8);
+            }
+
+        f32x4_t dk[4], dv[4];
+#pragma unroll
+        for (int f = 0; f < 4; ++f) dk[f] = dv[f] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+        for (int c2 = 0; c2 < nch; c2 += 2) {
+            Row<bf16_t> qa[2][2], ga[2][2];
+            float2 st[2][4];
+            uint2 mp[2];
+#pragma unroll
+            for (int ci = 0; ci < 2; ++ci) {
+                const int at = (c0 + c2 + ci) * 16;
+                const int off = (int)__umul24(a.cols[at + j], a.row_bytes) + feat_off;
+                buf_row(rQ, off, qa[ci][0]);
+                buf_row(rQ, off + 16, qa[ci][1]);
+                buf_row(rG, off, ga[ci][0]);
+                buf_row(rG, off + 16, ga[ci][1]);
+                const int4 u4 = *reinterpret_cast<const int4*>(a.cols + at + 4 * g);
+                st[ci][0] = buf_f2(rS, u4.x * 8);
+                st[ci][1] = buf_f2(rS, u4.y * 8);
+                st[ci][2] = buf_f2(rS, u4.z * 8);
+                st[ci][3] = buf_f2(rS, u4.w * 8);
+                mp[ci] = *reinterpret_cast<const uint2*>(a.map + ((int64_t)(c0 + c2 + ci) * 16 + j) * 16 + 4 * g);
+            }
+            wave_lds_sync();  // the previous pair's LDS reads are done
+            f32x4_t s4[2], d4[2];
+#pragma unroll
+            for (int ci = 0; ci < 2; ++ci) {
+                const bf16x8_t q0 = as_bf16x8(qa[ci][0]), q1 = as_bf16x8(qa[ci][1]);
+                s4[ci] = d4[ci] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                s4[ci] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(q0, kb0, s4[ci], 0, 0, 0);
+                s4[ci] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(q1, kb1, s4[ci], 0, 0, 0);
+                d4[ci] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ga[ci][0]), vb0, d4[ci], 0, 0, 0);
+                d4[ci] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ga[ci][1]), vb1, d4[ci], 0, 0, 0);
+#pragma unroll
+                for (int bc = 0; bc < kMaxBiasChunks; ++bc)
+                    if (bc < nbc) {
+                        f32x4_t b4 = {0.f, 0.f, 0.f, 0.f};
+                        b4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(q0, rb[bc][0], b4, 0, 0, 0);
+                        b4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(q1, rb[bc][1], b4, 0, 0, 0);
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) bias_s[(16 * ci + 4 * g + r) * bstride + 16 * bc + j] = b4[r];
+                    }
+                // the chunk's Q and dO rows, as B operands of the second products
+                uint2* dq = reinterpret_cast<uint2*>(q_s + (16 * ci + j) * kVStride + 16 * g);
+                uint2* dg = reinterpret_cast<uint2*>(g_s + (16 * ci + j) * kVStride + 16 * g);
+                dq[0] = make_uint2(qa[ci][0].w.x, qa[ci][0].w.y);
+                dq[1] = make_uint2(qa[ci][0].w.z, qa[ci][0].w.w);
+                dq[2] = make_uint2(qa[ci][1].w.x, qa[ci][1].w.y);
+                dq[3] = make_uint2(qa[ci][1].w.z, qa[ci][1].w.w);
+                dg[0] = make_uint2(ga[ci][0].w.x, ga[ci][0].w.y);
+                dg[1] = make_uint2(ga[ci][0].w.z, ga[ci][0].w.w);
+                dg[2] = make_uint2(ga[ci][1].w.x, ga[ci][1].w.y);
+                dg[3] = make_uint2(ga[ci][1].w.z, ga[ci][1].w.w);
+            }
+            wave_lds_sync();
+            float ds[2][4], pp[2][4];
+#pragma unroll
+            for (int ci = 0; ci < 2; ++ci) {
+                const int bid[4] = {(int)(short)(mp[ci].x & 0xFFFFu), (int)(short)(mp[ci].x >> 16),
+                                    (int)(short)(mp[ci].y & 0xFFFFu), (int)(short)(mp[ci].y >> 16)};
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float b = bias_s[(16 * ci + 4 * g + r) * bstride + max(bid[r], 0)];
+                    const float p = bid[r] >= 0 ? fast_exp2((s4[ci][r] + b) * qscale - st[ci][r].x) : 0.f;
+                    pp[ci][r] = p;
+                    ds[ci][r] = p * (d4[ci][r] - st[ci][r].y);
+                }
+            }
+            // dS and P as A operands, each as bf16 hi + lo: the sums run over up to thousands of
+            // queries and the tolerance is absolute, so 8 mantissa bits are not enough
+            uint32_t shi[4], slo[4], phi[4], plo[4];
+#pragma unroll
+            for (int ci = 0; ci < 2; ++ci) {
+                split_pack(ds[ci][0], ds[ci][1], shi[2 * ci], slo[2 * ci]);
+                split_pack(ds[ci][2], ds[ci][3], shi[2 * ci + 1], slo[2 * ci + 1]);
+                split_pack(pp[ci][0], pp[ci][1], phi[2 * ci], plo[2 * ci]);
+                split_pack(pp[ci][2], pp[ci][3], phi[2 * ci + 1], plo[2 * ci + 1]);
+            }
+            const u32x4 xsh = {shi[0], shi[1], shi[2], shi[3]}, xsl = {slo[0], slo[1], slo[2], slo[3]};
+            const u32x4 xph = {phi[0], phi[1], phi[2], phi[3]}, xpl = {plo[0], plo[1], plo[2], plo[3]};
+            const bf16x8_t sH = __builtin_bit_cast(bf16x8_t, xsh), sL = __builtin_bit_cast(bf16x8_t, xsl);
+            const bf16x8_t pH = __builtin_bit_cast(bf16x8_t, xph), pL = __builtin_bit_cast(bf16x8_t, xpl);
+#pragma unroll
+            for (int f = 0; f < 4; ++f) {
+                const bf16_t* qc = q_s + 16 * f + j;
+                const bf16_t* gc = g_s + 16 * f + j;
+                u32x4 qt, gt;
+                qt.x = (uint32_t)qc[(4 * g + 0) * kVStride] | ((uint32_t)qc[(4 * g + 1) * kVStride] << 16);
+                qt.y = (uint32_t)qc[(4 * g + 2) * kVStride] | ((uint32_t)qc[(4 * g + 3) * kVStride] << 16);
+                qt.z = (uint32_t)qc[(16 + 4 * g + 0) * kVStride] | ((uint32_t)qc[(16 + 4 * g + 1) * kVStride] << 16);
+                qt.w = (uint32_t)qc[(16 + 4 * g + 2) * kVStride] | ((uint32_t)qc[(16 + 4 * g + 3) * kVStride] << 16);
+                gt.x = (uint32_t)gc[(4 * g + 0) * kVStride] | ((uint32_t)gc[(4 * g + 1) * kVStride] << 16);
+                gt.y = (uint32_t)gc[(4 * g + 2) * kVStride] | ((uint32_t)gc[(4 * g + 3) * kVStride] << 16);
+                gt.z = (uint32_t)gc[(16 + 4 * g + 0) * kVStride] | ((uint32_t)gc[(16 + 4 * g + 1) * kVStride] << 16);
+                gt.w = (uint32_t)gc[(16 + 4 * g + 2) * kVStride] | ((uint32_t)gc[(16 + 4 * g + 3) * kVStride] << 16);
+                const bf16x8_t qB = __builtin_bit_cast(bf16x8_t, qt), gB = __builtin_bit_cast(bf16x8_t, gt);
+                dk[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sH, qB, dk[f], 0, 0, 0);
+                dk[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sL, qB, dk[f], 0, 0, 0);
+                dv[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pH, gB, dv[f], 0, 0, 0);
+                dv[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pL, gB, dv[f], 0, 0, 0);
+            }
+        }
+        // C[m = key][n = feature]: lane holds keys 4g..4g+3, feature 16f + j
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int key = 4 * g + r;
+            if (key < nkeys) {
+                if (part < 0) {
+                    const int64_t at = base + (int64_t)(node0 + key) * a.sn + j;
+#pragma unroll
+                    for (int f = 0; f < 4; ++f) {
+                        a.dK[at + 16 * f] = a.scale * dk[f][r];
+                        a.dV[at + 16 * f] = dv[f][r];
+                    }
+                } else {
+                    float* dst = a.part + (((int64_t)bh * a.num_part + part) * 16 + key) * (2 * kD) + j;
+#pragma unroll
+                    for (int f = 0; f < 4; ++f) {
+                        dst[16 * f] = a.scale * dk[f][r];
+                        dst[kD + 16 * f] = dv[f][r];
+                    }
+                }
+            }
+        }
+        wave_lds_sync();
+    }
+}
+
+// tiles whose query list was cut into several tasks: sum the partial (dK, dV) of the
+// tile's keys in task order.  One workgroup per (batch*head, tile); thread -> (key, feature pair).
+__global__ void __launch_bounds__(256) kv_tile_merge_kernel(const KeyArgs a, const int32_t* __restrict__ multi_tile,
+                                                            const int32_t* __restrict__ multi_ptr, int num_multi) {
+    const int bh = blockIdx.x / num_multi, mt = blockIdx.x - bh * num_multi;
+    const int kt = multi_tile[mt];
+    const int node0 = a.tile_node0[kt], nkeys = a.tile_info[kt] >> 8;
+    const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
+    for (int i = threadIdx.x; i < nkeys * kD; i += blockDim.x) {
+        const int key = i >> 6, f = i & 63;
+        float sk = 0.f, sv = 0.f;
+        for (int p = multi_ptr[mt]; p < multi_ptr[mt + 1]; ++p) {
+            const float* src = a.part + (((int64_t)bh * a.num_part + p) * 16 + key) * (2 * kD) + f;
+            sk += src[0];
+            sv += src[kD];
+        }
+        const int64_t at = base + (int64_t)(node0 + key) * a.sn + f;
+        a.dK[at] = sk;
+        a.dV[at] = sv;
+    }
+}
+
+// nodes no one attends to (levels above the coarsest contextual level): zero gradients
+__global__ void kv_zero_rows_kernel(const KeyArgs a, int first_row) {
+    const int rows = a.N - first_row;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (int64_t)a.BH * rows * kD) return;
+    const int f = (int)(i & 63);
+    const int64_t rr = i >> 6;
+    const int bh = (int)(rr / rows), row = first_row + (int)(rr - (int64_t)bh * rows);
+    const int64_t at = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh + (int64_t)row * a.sn + f;
+    a.dK[at] = 0.f;
+    a.dV[at] = 0.f;
+}
+
 // key nodes cut into several segments: sum the (dK, dV) partials in segment order
 __global__ void __launch_bounds__(256) bwd_kv_merge_kernel(const AttnArgs a, const int32_t* __restrict__ multi_row,
                                                            const int32_t* __restrict__ multi_ptr, int num_multi) {
@@ -1628,6 +1866,8 @@ struct BwdPlan {
     int drel_rows = 0;        // d_rel rows token rows can touch
     bool drel_mfma = false;   // bf16 tensors: rel_grad_mfma_kernel; fp32: rel_grad_kernel
     bool q_tiles = false;     // query side of token rows on dense tiles (bwd_q_tile_kernel)
+    bool kv_tiles = false;    // key side on dense tiles of key nodes (bwd_kv_tile_kernel)
+    size_t kv_lds = 0;
     int drel_ipw = 32;        // ids per wavefront: 8, 16 or 32
     int drel_block = 32;      // token rows per block
     int drel_grid_x = 8, drel_grid_y = 1;
@@ -1652,6 +1892,10 @@ int plan_bwd(const bpt_graph* g, const bpt_shape_t* s, BwdPlan* p) {
             p->q_tiles = true;
             p->drel_lds += (size_t)kD * (nids + 8) * sizeof(bf16_t);  // Rel^T
         }
+        if (g->ktiles.num_tasks > 0 && g->ktiles.nb_pad <= 16 * kMaxBiasChunks) {
+            p->kv_lds = (size_t)kTileWaves * (32 * (g->ktiles.nb_pad + 1) * sizeof(float) + 64 * kVStride * sizeof(bf16_t));
+            p->kv_tiles = p->kv_lds <= lim.lds;
+        }
         p->drel_grid_y = (p->drel_rows + kRgIds - 1) / kRgIds;
         blocks = (int64_t)s->B * s->H * ((g->n + kRgRows - 1) / kRgRows);
     } else {
@@ -1673,7 +1917,8 @@ int plan_bwd(const bpt_graph* g, const bpt_shape_t* s, BwdPlan* p) {
     p->off_qpart = off;
     off += align_up(bh * std::max(g->fwd.num_part, g->fwd_span.num_part) * kQPartStride * sizeof(float));
     p->off_kvpart = off;
-    off += align_up(bh * g->tr.num_part * 2 * kD * sizeof(float));
+    off += align_up(bh * std::max<size_t>(g->tr.num_part, p->kv_tiles ? (size_t)g->ktiles.num_part * 16 : 0) * 2 * kD *
+                    sizeof(float));
     p->off_drel = off;
     off += align_up((size_t)p->drel_grid_x * p->drel_rows * kD * sizeof(float));
     p->total = off;
@@ -1751,11 +1996,70 @@ int run_bwd_q(const bpt_graph* g, const BwdPlan& p, AttnArgs& a, hipStream_t st)
     return BPT_OK;
 }
 
+// bf16 key side on dense tiles of key nodes
+int run_bwd_kv_tiles(const bpt_graph* g, const BwdPlan& p, const AttnArgs& a, const DeviceLimits& lim, hipStream_t st) {
+    const KeyTiles& kt = g->ktiles;
+    KeyArgs t = {};
+    t.Q = static_cast<const bf16_t*>(a.Q);
+    t.K = static_cast<const bf16_t*>(a.K);
+    t.V = static_cast<const bf16_t*>(a.V);
+    t.rel = static_cast<const bf16_t*>(a.rel);
+    t.dout = static_cast<const bf16_t*>(a.dout);
+    t.stat = a.stat;
+    t.dK = a.dK;
+    t.dV = a.dV;
+    t.part = a.part;
+    t.sb = a.sb;
+    t.sh = a.sh;
+    t.sn = a.sn;
+    t.BH = a.BH;
+    t.H = a.H;
+    t.N = a.N;
+    t.num_levels = g->num_levels;
+    t.scale = a.scale;
+    t.row_bytes = a.row_bytes;
+    t.slab_bytes = a.slab_bytes;
+    t.tile_node0 = kt.tile_node0;
+    t.tile_info = kt.tile_info;
+    t.cols = kt.cols;
+    t.task_tile = kt.task_tile;
+    t.task_c0 = kt.task_c0;
+    t.task_nch = kt.task_nch;
+    t.task_part = kt.task_part;
+    t.map = kt.map;
+    t.num_tasks = kt.num_tasks;
+    t.num_part = kt.num_part;
+    t.nb_pad = kt.nb_pad;
+    t.W = g->rel_width;
+    t.zero = g->k + 1;
+    if (p.kv_lds > 65536)
+        BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_kv_tile_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.kv_lds));
+    int per_cu = 0;
+    BPT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, bwd_kv_tile_kernel, kTileThreads, p.kv_lds));
+    const int grid = std::max(8, lim.cus * std::max(1, per_cu) / 8 * 8);
+    hipLaunchKernelGGL(bwd_kv_tile_kernel, dim3(grid), dim3(kTileThreads), p.kv_lds, st, t);
+    BPT_HIP(hipGetLastError());
+    if (kt.num_multi > 0) {
+        hipLaunchKernelGGL(kv_tile_merge_kernel, dim3(a.BH * kt.num_multi), dim3(256), 0, st, t, kt.multi_tile,
+                           kt.multi_ptr, kt.num_multi);
+        BPT_HIP(hipGetLastError());
+    }
+    const int64_t zero_elems = (int64_t)a.BH * (a.N - kt.first_uncovered) * kD;
+    if (zero_elems > 0) {
+        hipLaunchKernelGGL(kv_zero_rows_kernel, dim3((unsigned)((zero_elems + 255) / 256)), dim3(256), 0, st, t,
+                           kt.first_uncovered);
+        BPT_HIP(hipGetLastError());
+    }
+    return BPT_OK;
+}
+
 template <typename T>
-int run_bwd_kv(const bpt_graph* g, AttnArgs& a, hipStream_t st) {
+int run_bwd_kv(const bpt_graph* g, const BwdPlan& p, AttnArgs& a, hipStream_t st) {
     DeviceLimits lim;
     int rc = device_limits(g, &lim);
     if (rc) return rc;
+    if (p.kv_tiles) return run_bwd_kv_tiles(g, p, a, lim, st);
     a.ptr = g->t_ptr;
     a.ia = g->t_src;
     a.ib = g->t_rel;
@@ -1823,7 +2127,7 @@ int backward(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q, const vo
     }
     if (stages & kStageKV) {
         a.part = reinterpret_cast<float*>(ws + p.off_kvpart);
-        if ((rc = bf ? run_bwd_kv<bf16_t>(g, a, st) : run_bwd_kv<float>(g, a, st))) return rc;
+        if ((rc = bf ? run_bwd_kv<bf16_t>(g, p, a, st) : run_bwd_kv<float>(g, p, a, st))) return rc;
     }
     return BPT_OK;
 }

@@ -505,6 +505,131 @@ int make_token_tiles(int32_t n, int32_t k, int32_t num_levels, const std::vector
     return BPT_OK;
 }
 
+void free_key_tiles(KeyTiles& t) {
+    (void)hipFree(t.tile_node0);
+    (void)hipFree(t.tile_info);
+    (void)hipFree(t.cols);
+    (void)hipFree(t.map);
+    (void)hipFree(t.task_tile);
+    (void)hipFree(t.task_c0);
+    (void)hipFree(t.task_nch);
+    (void)hipFree(t.task_part);
+    (void)hipFree(t.multi_tile);
+    (void)hipFree(t.multi_ptr);
+    t = KeyTiles();
+}
+
+// Key-tile metadata from the token rows of the CSR (span rows are closed form: span
+// (l, m) attends exactly its tokens).  The queries of a tile are bucketed as tokens
+// left of the keys, tokens right of them (for token keys both merge with the keys
+// themselves into one range), then the ancestor levels; a bucket's union is its node
+// range [min, max].  Tile-local relative-position ids: order + k+1 for contextual and
+// self edges, W + l' - 1 for the affiliated edge of the ancestor at level l'.
+int make_key_tiles(int32_t n, int32_t k, int32_t num_levels, int32_t ctx_levels, const std::vector<int32_t>& ptr,
+                   const std::vector<int32_t>& col, const std::vector<int32_t>& rel, KeyTiles& out) {
+    const int32_t W = 2 * (k + 1) + 1, zero = k + 1;
+    if (W + num_levels > 32767) return BPT_OK;
+    std::vector<int32_t> tile_base(ctx_levels + 1, 0);
+    for (int32_t l = 0; l < ctx_levels; ++l) tile_base[l + 1] = tile_base[l] + ((n >> l) + 15) / 16;
+    const int32_t nkt = tile_base[ctx_levels];
+    // pass 1: query ranges per tile; bucket 0 = tokens left of the keys (or all tokens for token keys), 1 = right
+    std::vector<int32_t> lo(2 * (size_t)nkt, INT32_MAX), hi(2 * (size_t)nkt, -1);
+    std::vector<int32_t> key_tile((size_t)ptr[n]);  // tile of every token-row edge's key
+    for (int32_t u = 0; u < n; ++u)
+        for (int32_t x = ptr[u]; x < ptr[u + 1]; ++x) {
+            const int32_t v = col[x], l = rel[x] / W, ord = rel[x] % W - zero;
+            const int32_t kt = tile_base[l] + ((v - (int32_t)level_offset(n, l)) >> 4);
+            key_tile[x] = kt;
+            const size_t b = 2 * (size_t)kt + ((l > 0 && ord < 0) ? 1 : 0);  // ord < 0: key in u's left context
+            lo[b] = std::min(lo[b], u);
+            hi[b] = std::max(hi[b], u);
+        }
+    // layout: chunks per tile, then columns
+    std::vector<int32_t> chunk_ptr(1, 0), first((size_t)2 * nkt + 0), tile_node0(nkt), tile_info(nkt), anc_first(nkt, 0);
+    std::vector<int32_t> cols;
+    size_t total_chunks = 0;
+    for (int32_t l = 0; l < ctx_levels; ++l)
+        for (int32_t kt = tile_base[l]; kt < tile_base[l + 1]; ++kt) {
+            const int32_t m0 = (kt - tile_base[l]) * 16, nkeys = std::min(16, (n >> l) - m0);
+            tile_node0[kt] = (int32_t)level_offset(n, l) + m0;
+            tile_info[kt] = l | (nkeys << 8);
+            int32_t total = 0;
+            for (int32_t b = 0; b < 2; ++b) {
+                first[2 * (size_t)kt + b] = total;
+                if (hi[2 * (size_t)kt + b] >= 0) total += hi[2 * (size_t)kt + b] - lo[2 * (size_t)kt + b] + 1;
+            }
+            anc_first[kt] = total;
+            if (l == 0)  // ancestors of the tile's tokens, level by level
+                for (int32_t la = 1; la < num_levels; ++la) total += ((m0 + nkeys - 1) >> la) - (m0 >> la) + 1;
+            int32_t nch = (total + 15) / 16;
+            nch += nch & 1;
+            total_chunks += nch;
+            if (total_chunks * 512 > ((size_t)512 << 20)) return BPT_OK;  // too large: no tile path
+            const size_t c0 = cols.size();
+            cols.resize(c0 + (size_t)nch * 16, tile_node0[kt]);  // padding columns: a real node, masked
+            size_t at = c0;
+            for (int32_t b = 0; b < 2; ++b)
+                for (int32_t u = lo[2 * (size_t)kt + b]; hi[2 * (size_t)kt + b] >= 0 && u <= hi[2 * (size_t)kt + b]; ++u)
+                    cols[at++] = u;
+            if (l == 0)
+                for (int32_t la = 1; la < num_levels; ++la)
+                    for (int32_t a = m0 >> la; a <= ((m0 + nkeys - 1) >> la); ++a)
+                        cols[at++] = (int32_t)level_offset(n, la) + a;
+            chunk_ptr.push_back((int32_t)(cols.size() / 16));
+        }
+    // pass 2: maps
+    std::vector<int16_t> map(cols.size() * 16, (int16_t)-1);
+    for (int32_t u = 0; u < n; ++u)
+        for (int32_t x = ptr[u]; x < ptr[u + 1]; ++x) {
+            const int32_t kt = key_tile[x], l = rel[x] / W, w = rel[x] % W;
+            const size_t b = 2 * (size_t)kt + ((l > 0 && w - zero < 0) ? 1 : 0);
+            const int32_t slot = first[b] + u - lo[b];
+            const int32_t key = (col[x] - tile_node0[kt]);
+            map[((size_t)chunk_ptr[kt] + (slot >> 4)) * 256 + key * 16 + (slot & 15)] = (int16_t)w;
+        }
+    for (int32_t kt = tile_base[0]; kt < tile_base[1]; ++kt) {  // affiliated edges: ancestor at level la <- token
+        const int32_t m0 = (kt - tile_base[0]) * 16, nkeys = tile_info[kt] >> 8;
+        int32_t slot0 = anc_first[kt];
+        for (int32_t la = 1; la < num_levels; ++la) {
+            for (int32_t key = 0; key < nkeys; ++key) {
+                const int32_t slot = slot0 + ((m0 + key) >> la) - (m0 >> la);
+                map[((size_t)chunk_ptr[kt] + (slot >> 4)) * 256 + key * 16 + (slot & 15)] = (int16_t)(W + la - 1);
+            }
+            slot0 += ((m0 + nkeys - 1) >> la) - (m0 >> la) + 1;
+        }
+    }
+    // tasks
+    std::vector<int32_t> task_tile, task_c0, task_nch, task_part, multi_tile, multi_ptr(1, 0);
+    int32_t parts = 0;
+    for (int32_t kt = 0; kt < nkt; ++kt) {
+        const int32_t c0 = chunk_ptr[kt], nch = chunk_ptr[kt + 1] - c0;
+        const int32_t ntask = std::max(1, (nch + kKeyTaskChunks - 1) / kKeyTaskChunks);
+        for (int32_t t = 0; t < ntask; ++t) {
+            task_tile.push_back(kt);
+            task_c0.push_back(c0 + t * kKeyTaskChunks);
+            task_nch.push_back(std::max(0, std::min(kKeyTaskChunks, nch - t * kKeyTaskChunks)));
+            task_part.push_back(ntask > 1 ? parts++ : -1);
+        }
+        if (ntask > 1) {
+            multi_tile.push_back(kt);
+            multi_ptr.push_back(parts);
+        }
+    }
+    out.nb_pad = (W + num_levels - 1 + 15) & ~15;
+    out.first_uncovered = (int32_t)level_offset(n, ctx_levels);
+    out.num_multi = (int32_t)multi_tile.size();
+    out.num_part = parts;
+    int rc;
+    if ((rc = upload(tile_node0, &out.tile_node0)) || (rc = upload(tile_info, &out.tile_info)) ||
+        (rc = upload(cols, &out.cols)) || (rc = upload(map, &out.map)) || (rc = upload(task_tile, &out.task_tile)) ||
+        (rc = upload(task_c0, &out.task_c0)) || (rc = upload(task_nch, &out.task_nch)) ||
+        (rc = upload(task_part, &out.task_part)) || (rc = upload(multi_tile, &out.multi_tile)) ||
+        (rc = upload(multi_ptr, &out.multi_ptr)))
+        return rc;
+    out.num_tasks = (int32_t)task_tile.size();
+    return BPT_OK;
+}
+
 int build(int32_t n, int32_t k, int32_t causal, hipStream_t st, bpt_graph* g) {
     const int num_levels = 32 - __builtin_clz((unsigned)n);  // log2(n) + 1
     const int num_nodes = 2 * n - 1;
@@ -605,6 +730,8 @@ int build(int32_t n, int32_t k, int32_t causal, hipStream_t st, bpt_graph* g) {
         BPT_HIP(hipStreamSynchronize(st));
         if ((rc = make_token_tiles(n, k, num_levels, h_ptr, h_col, h_rel, g->tiles))) return rc;
         if (g->tiles.num_tiles > 0 && (rc = make_schedule(h_ptr, n, n, g->fwd_span))) return rc;
+        if (g->tiles.num_tiles > 0 && (rc = make_key_tiles(n, k, num_levels, g->ctx_levels, h_ptr, h_col, h_rel, g->ktiles)))
+            return rc;
     }
     return BPT_OK;
 }
@@ -627,6 +754,7 @@ void bpt_graph_destroy(bpt_graph_t* g) {
     bpt::free_schedule(g->tr);
     bpt::free_schedule(g->fwd_span);
     bpt::free_tiles(g->tiles);
+    bpt::free_key_tiles(g->ktiles);
     delete g;
 }
 

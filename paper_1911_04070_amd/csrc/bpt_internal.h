@@ -44,6 +44,29 @@ struct TokenTiles {
     int32_t* cid_to_id = nullptr;  // [num_cids] compact id -> row of the relative-position table
 };
 
+// Dense tiles over the key nodes, for the matrix-core key-side backward.  A tile is up
+// to 16 consecutive nodes of one level; its columns are the nodes that attend to any
+// of them (tokens on either side, and for token keys their ancestor spans), in
+// ascending node id, in chunks of 16 (an even number per tile).  A tile's chunk list
+// is cut into tasks of at most kKeyTaskChunks chunks; tiles with several tasks are
+// summed by a merge kernel in task order.
+constexpr int kKeyTaskChunks = 32;
+struct KeyTiles {
+    int32_t num_tasks = 0, num_multi = 0, num_part = 0;
+    int32_t nb_pad = 0;             // relative-position ids a tile can meet, padded to 16
+    int32_t first_uncovered = 0;    // nodes from here on have no in-edges (levels without contextual edges)
+    int32_t* tile_node0 = nullptr;  // [tiles] first key node
+    int32_t* tile_info = nullptr;   // [tiles] level | valid keys << 8
+    int32_t* cols = nullptr;        // [chunks][16] query node of a column
+    int16_t* map = nullptr;         // [chunks][16 keys][16 columns] tile-local relative-position id, or -1
+    int32_t* task_tile = nullptr;   // [tasks]
+    int32_t* task_c0 = nullptr;     // [tasks] first chunk
+    int32_t* task_nch = nullptr;    // [tasks] chunks (even)
+    int32_t* task_part = nullptr;   // [tasks] partial slot, or -1 if the tile has one task
+    int32_t* multi_tile = nullptr;  // [num_multi] tiles with several tasks
+    int32_t* multi_ptr = nullptr;   // [num_multi+1] their partial slots
+};
+
 }  // namespace bpt
 
 struct bpt_graph {
@@ -60,6 +83,7 @@ struct bpt_graph {
     bpt::Schedule fwd, tr;
     bpt::Schedule fwd_span;   // span rows only (used with the token tiles)
     bpt::TokenTiles tiles;
+    bpt::KeyTiles ktiles;
 };
 
 #define BPT_HIP(expr)                                  \
