@@ -143,6 +143,17 @@ int bpt_attn_bwd_key_side(const bpt_graph_t* g, const bpt_shape_t* s, const void
                           const void* dout, float* dK, float* dV, void* workspace,
                           size_t workspace_bytes, void* stream);
 
+/* For benchmarks and tuning (not part of the paper's method): while enabled, every
+ * kernel the library launches is bracketed by two HIP events on the launch stream.
+ * bpt_profile_enable(on != 0) starts a fresh record, bpt_profile_enable(0) drops it.
+ * bpt_profile_report waits for the recorded events and writes one line per kernel,
+ * "name launches total_ms", NUL-terminated and truncated to `capacity`, into the host
+ * buffer `buf` (may be NULL); it returns the bytes the full text needs, or -1 on a
+ * HIP error.  Enabling creates events (allocations) on every launch and the state is
+ * global and not thread-safe: leave it off outside measurements. */
+int bpt_profile_enable(int on);
+int64_t bpt_profile_report(char* buf, size_t capacity);
+
 /* Static, never NULL. */
 const char* bpt_strerror(int status);
 

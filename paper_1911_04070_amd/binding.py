@@ -22,7 +22,8 @@ BPT_OK, BPT_ERR_INVALID_ARG, BPT_ERR_UNSUPPORTED, BPT_ERR_ALLOC, BPT_ERR_LAUNCH,
 EXPORTS = [
     "bpt_build_graph", "bpt_graph_info", "bpt_graph_csr", "bpt_graph_transposed", "bpt_graph_to_host",
     "bpt_graph_transposed_to_host", "bpt_graph_destroy", "bpt_attn_fwd_workspace", "bpt_attn_bwd_workspace",
-    "bpt_attn_fwd", "bpt_attn_bwd", "bpt_attn_bwd_query_side", "bpt_attn_bwd_key_side", "bpt_strerror",
+    "bpt_attn_fwd", "bpt_attn_bwd", "bpt_attn_bwd_query_side", "bpt_attn_bwd_key_side", "bpt_profile_enable",
+    "bpt_profile_report", "bpt_strerror",
 ]
 
 
@@ -79,6 +80,10 @@ def load_library() -> ctypes.CDLL:
     L.bpt_attn_bwd_query_side.argtypes = [vp, P(BptShape)] + [vp] * 9 + [sz, vp]
     L.bpt_attn_bwd_key_side.restype = ctypes.c_int
     L.bpt_attn_bwd_key_side.argtypes = [vp, P(BptShape)] + [vp] * 9 + [sz, vp]
+    L.bpt_profile_enable.restype = ctypes.c_int
+    L.bpt_profile_enable.argtypes = [ctypes.c_int]
+    L.bpt_profile_report.restype = ctypes.c_int64
+    L.bpt_profile_report.argtypes = [ctypes.c_char_p, sz]
     L.bpt_strerror.restype = ctypes.c_char_p
     L.bpt_strerror.argtypes = [ctypes.c_int]
     _lib = L
@@ -269,6 +274,25 @@ def bpt_attn_bwd_key_side(g: Graph, Q, K, V, rel, lse, dout, dK, dV, workspace, 
                                    workspace.numel() * workspace.element_size(), _stream_ptr()),
            "bpt_attn_bwd_key_side")
     return dK, dV
+
+
+def bpt_profile_enable(on: bool) -> None:
+    _check(load_library().bpt_profile_enable(int(bool(on))), "bpt_profile_enable")
+
+
+def bpt_profile_report() -> dict:
+    """{kernel name: (launches, total milliseconds)} of the launches recorded since profiling was enabled."""
+    L = load_library()
+    need = int(L.bpt_profile_report(None, 0))
+    if need < 0:
+        raise BptError(BPT_ERR_LAUNCH, "bpt_profile_report")
+    buf = ctypes.create_string_buffer(max(need, 1))
+    L.bpt_profile_report(buf, need)
+    out = {}
+    for line in buf.value.decode().splitlines():
+        name, calls, ms = line.rsplit(" ", 2)
+        out[name] = (int(calls), float(ms))
+    return out
 
 
 def workspace_bytes(g: Graph, like: torch.Tensor, scale: Optional[float] = None) -> Tuple[int, int]:

@@ -1717,8 +1717,8 @@ int persistent_grid(K kernel, int threads, size_t lds, const DeviceLimits& lim, 
 }
 
 template <typename K>
-int launch(K kernel, int grid, int threads, size_t lds, hipStream_t st, const AttnArgs& a) {
-    hipLaunchKernelGGL(kernel, dim3(grid), dim3(threads), lds, st, a);
+int launch(const char* name, K kernel, int grid, int threads, size_t lds, hipStream_t st, const AttnArgs& a) {
+    BPT_LAUNCH(name, kernel, dim3(grid), dim3(threads), lds, st, a);
     BPT_HIP(hipGetLastError());
     return BPT_OK;
 }
@@ -1761,14 +1761,14 @@ size_t tile_lds_bytes(const bpt_graph* g, int* cid_pad, int* bias_stride) {
 void fill_tile_args(TileArgs& t, const bpt_graph* g, const AttnArgs& a, int cid_pad, int bias_stride);
 
 template <typename K>
-int launch_tiles(K kernel, const TileArgs& t, const DeviceLimits& lim, size_t lds, hipStream_t st) {
+int launch_tiles(const char* name, K kernel, const TileArgs& t, const DeviceLimits& lim, size_t lds, hipStream_t st) {
     if (lds > 65536)
         BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                     (int)lds));
     int per_cu = 0;
     BPT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kTileThreads, lds));
     const int grid = std::max(8, lim.cus * std::max(1, per_cu) / 8 * 8);
-    hipLaunchKernelGGL(kernel, dim3(grid), dim3(kTileThreads), lds, st, t);
+    BPT_LAUNCH(name, kernel, dim3(grid), dim3(kTileThreads), lds, st, t);
     BPT_HIP(hipGetLastError());
     return BPT_OK;
 }
@@ -1779,7 +1779,7 @@ int run_bwd_q_tiles(const bpt_graph* g, const AttnArgs& a, const DeviceLimits& l
     const size_t lds = tile_lds_bytes(g, &cid_pad, &bias_stride);
     TileArgs t = {};
     fill_tile_args(t, g, a, cid_pad, bias_stride);
-    return launch_tiles(bwd_q_tile_kernel, t, lim, lds, st);
+    return launch_tiles("bwd_q_tile_kernel", bwd_q_tile_kernel, t, lim, lds, st);
 }
 
 void fill_tile_args(TileArgs& t, const bpt_graph* g, const AttnArgs& a, int cid_pad, int bias_stride) {
@@ -1821,7 +1821,7 @@ int run_fwd_tiles(const bpt_graph* g, AttnArgs& a, const DeviceLimits& lim, size
                   hipStream_t st) {
     TileArgs t = {};
     fill_tile_args(t, g, a, cid_pad, bias_stride);
-    return launch_tiles(fwd_tile_kernel, t, lim, lds, st);
+    return launch_tiles("fwd_tile_kernel", fwd_tile_kernel, t, lim, lds, st);
 }
 
 template <typename T>
@@ -1845,16 +1845,16 @@ int run_fwd(const bpt_graph* g, AttnArgs& a, hipStream_t st) {
     int grid = 8;
     if (rel_lds) {
         if ((rc = persistent_grid(fwd_kernel<T, true>, kThreads, lds, lim, &grid))) return rc;
-        rc = launch(fwd_kernel<T, true>, grid, kThreads, lds, st, a);
+        rc = launch("fwd_kernel", fwd_kernel<T, true>, grid, kThreads, lds, st, a);
     } else {
         if ((rc = persistent_grid(fwd_kernel<T, false>, kThreads, 0, lim, &grid))) return rc;
-        rc = launch(fwd_kernel<T, false>, grid, kThreads, 0, st, a);
+        rc = launch("fwd_kernel", fwd_kernel<T, false>, grid, kThreads, 0, st, a);
     }
     if (rc) return rc;
     const Schedule& sc = a.seg_row == g->fwd_span.seg_row ? g->fwd_span : g->fwd;
     if (sc.num_multi > 0) {
         const int items = a.BH * sc.num_multi;
-        hipLaunchKernelGGL(fwd_merge_kernel<T>, dim3((items + 3) / 4), dim3(256), 0, st, a, sc.multi_row, sc.multi_ptr,
+        BPT_LAUNCH("fwd_merge_kernel", fwd_merge_kernel<T>, dim3((items + 3) / 4), dim3(256), 0, st, a, sc.multi_row, sc.multi_ptr,
                            sc.num_multi);
         BPT_HIP(hipGetLastError());
     }
@@ -1930,7 +1930,7 @@ int launch_rel_grad(const BwdPlan& p, hipStream_t st, const AttnArgs& a) {
     if (p.drel_lds > 65536)
         BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rel_grad_kernel<T, IPW>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.drel_lds));
-    hipLaunchKernelGGL((rel_grad_kernel<T, IPW>), dim3(p.drel_grid_x, p.drel_grid_y), dim3(kThreads), p.drel_lds, st,
+    BPT_LAUNCH("rel_grad_kernel", (rel_grad_kernel<T, IPW>), dim3(p.drel_grid_x, p.drel_grid_y), dim3(kThreads), p.drel_lds, st,
                        a);
     BPT_HIP(hipGetLastError());
     return BPT_OK;
@@ -1961,15 +1961,15 @@ int run_bwd_q(const bpt_graph* g, const BwdPlan& p, AttnArgs& a, hipStream_t st)
     int grid = 8;
     if (rel_lds) {
         if ((rc = persistent_grid(bwd_q_kernel<T, true>, kThreads, rel_b, lim, &grid))) return rc;
-        rc = launch(bwd_q_kernel<T, true>, grid, kThreads, rel_b, st, a);
+        rc = launch("bwd_q_kernel", bwd_q_kernel<T, true>, grid, kThreads, rel_b, st, a);
     } else {
         if ((rc = persistent_grid(bwd_q_kernel<T, false>, kThreads, 0, lim, &grid))) return rc;
-        rc = launch(bwd_q_kernel<T, false>, grid, kThreads, 0, st, a);
+        rc = launch("bwd_q_kernel", bwd_q_kernel<T, false>, grid, kThreads, 0, st, a);
     }
     if (rc) return rc;
     if (sc->num_multi > 0) {
         const int items = a.BH * sc->num_multi;
-        hipLaunchKernelGGL(bwd_q_merge_kernel, dim3((items + 3) / 4), dim3(256), 0, st, a, sc->multi_row,
+        BPT_LAUNCH("bwd_q_merge_kernel", bwd_q_merge_kernel, dim3((items + 3) / 4), dim3(256), 0, st, a, sc->multi_row,
                            sc->multi_ptr, sc->num_multi);
         BPT_HIP(hipGetLastError());
     }
@@ -1978,10 +1978,10 @@ int run_bwd_q(const bpt_graph* g, const BwdPlan& p, AttnArgs& a, hipStream_t st)
             BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rel_grad_mfma_kernel<true>),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.drel_lds));
         if (p.q_tiles)
-            hipLaunchKernelGGL(rel_grad_mfma_kernel<true>, dim3(p.drel_grid_x, p.drel_grid_y), dim3(kThreads),
+            BPT_LAUNCH("rel_grad_mfma_kernel", rel_grad_mfma_kernel<true>, dim3(p.drel_grid_x, p.drel_grid_y), dim3(kThreads),
                                p.drel_lds, st, a);
         else
-            hipLaunchKernelGGL(rel_grad_mfma_kernel<false>, dim3(p.drel_grid_x, p.drel_grid_y), dim3(kThreads),
+            BPT_LAUNCH("rel_grad_mfma_kernel", rel_grad_mfma_kernel<false>, dim3(p.drel_grid_x, p.drel_grid_y), dim3(kThreads),
                                p.drel_lds, st, a);
         BPT_HIP(hipGetLastError());
         rc = BPT_OK;
@@ -1990,7 +1990,7 @@ int run_bwd_q(const bpt_graph* g, const BwdPlan& p, AttnArgs& a, hipStream_t st)
                              : p.drel_ipw == 16 ? launch_rel_grad<T, 16>(p, st, a) : launch_rel_grad<T, 32>(p, st, a);
     }
     if (rc) return rc;
-    hipLaunchKernelGGL(drel_reduce_kernel, dim3(a.rel_rows), dim3(1024), 0, st, a.drel_part, p.drel_grid_x,
+    BPT_LAUNCH("drel_reduce_kernel", drel_reduce_kernel, dim3(a.rel_rows), dim3(1024), 0, st, a.drel_part, p.drel_grid_x,
                        p.drel_rows, a.d_rel);
     BPT_HIP(hipGetLastError());
     return BPT_OK;
@@ -2038,16 +2038,16 @@ int run_bwd_kv_tiles(const bpt_graph* g, const BwdPlan& p, const AttnArgs& a, co
     int per_cu = 0;
     BPT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, bwd_kv_tile_kernel, kTileThreads, p.kv_lds));
     const int grid = std::max(8, lim.cus * std::max(1, per_cu) / 8 * 8);
-    hipLaunchKernelGGL(bwd_kv_tile_kernel, dim3(grid), dim3(kTileThreads), p.kv_lds, st, t);
+    BPT_LAUNCH("bwd_kv_tile_kernel", bwd_kv_tile_kernel, dim3(grid), dim3(kTileThreads), p.kv_lds, st, t);
     BPT_HIP(hipGetLastError());
     if (kt.num_multi > 0) {
-        hipLaunchKernelGGL(kv_tile_merge_kernel, dim3(a.BH * kt.num_multi), dim3(256), 0, st, t, kt.multi_tile,
+        BPT_LAUNCH("kv_tile_merge_kernel", kv_tile_merge_kernel, dim3(a.BH * kt.num_multi), dim3(256), 0, st, t, kt.multi_tile,
                            kt.multi_ptr, kt.num_multi);
         BPT_HIP(hipGetLastError());
     }
     const int64_t zero_elems = (int64_t)a.BH * (a.N - kt.first_uncovered) * kD;
     if (zero_elems > 0) {
-        hipLaunchKernelGGL(kv_zero_rows_kernel, dim3((unsigned)((zero_elems + 255) / 256)), dim3(256), 0, st, t,
+        BPT_LAUNCH("kv_zero_rows_kernel", kv_zero_rows_kernel, dim3((unsigned)((zero_elems + 255) / 256)), dim3(256), 0, st, t,
                            kt.first_uncovered);
         BPT_HIP(hipGetLastError());
     }
@@ -2071,15 +2071,15 @@ int run_bwd_kv(const bpt_graph* g, const BwdPlan& p, AttnArgs& a, hipStream_t st
     int grid = 8;
     if (rel_lds) {
         if ((rc = persistent_grid(bwd_kv_kernel<T, true>, kThreads, rel_b, lim, &grid))) return rc;
-        rc = launch(bwd_kv_kernel<T, true>, grid, kThreads, rel_b, st, a);
+        rc = launch("bwd_kv_kernel", bwd_kv_kernel<T, true>, grid, kThreads, rel_b, st, a);
     } else {
         if ((rc = persistent_grid(bwd_kv_kernel<T, false>, kThreads, 0, lim, &grid))) return rc;
-        rc = launch(bwd_kv_kernel<T, false>, grid, kThreads, 0, st, a);
+        rc = launch("bwd_kv_kernel", bwd_kv_kernel<T, false>, grid, kThreads, 0, st, a);
     }
     if (rc) return rc;
     if (g->tr.num_multi > 0) {
         const int items = a.BH * g->tr.num_multi;
-        hipLaunchKernelGGL(bwd_kv_merge_kernel, dim3((items + 3) / 4), dim3(256), 0, st, a, g->tr.multi_row,
+        BPT_LAUNCH("bwd_kv_merge_kernel", bwd_kv_merge_kernel, dim3((items + 3) / 4), dim3(256), 0, st, a, g->tr.multi_row,
                            g->tr.multi_ptr, g->tr.num_multi);
         BPT_HIP(hipGetLastError());
     }

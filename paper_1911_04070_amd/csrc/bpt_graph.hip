@@ -9,7 +9,11 @@
 //   t_count        per token-row edge: in-degree and first query on each side of the key
 //   t_fill         closed-form slot of every edge in the transposed adjacency
 #include <algorithm>
+#include <cstdio>
+#include <cstring>
 #include <new>
+#include <string>
+#include <utility>
 #include <vector>
 
 #include "bpt_internal.h"
@@ -739,7 +743,75 @@ int build(int32_t n, int32_t k, int32_t causal, hipStream_t st, bpt_graph* g) {
 }  // namespace
 }  // namespace bpt
 
+namespace bpt {
+namespace prof {
+namespace {
+struct Rec {
+    const char* name;
+    hipEvent_t a, b;
+};
+bool g_on = false;
+std::vector<Rec> g_recs;
+void clear() {
+    for (Rec& r : g_recs) {
+        (void)hipEventDestroy(r.a);
+        (void)hipEventDestroy(r.b);
+    }
+    g_recs.clear();
+}
+}  // namespace
+bool enabled() { return g_on; }
+void begin(const char* name, hipStream_t st) {
+    Rec r{name, nullptr, nullptr};
+    if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) return;
+    (void)hipEventRecord(r.a, st);
+    g_recs.push_back(r);
+}
+void end(hipStream_t st) {
+    if (!g_recs.empty()) (void)hipEventRecord(g_recs.back().b, st);
+}
+}  // namespace prof
+}  // namespace bpt
+
 extern "C" {
+
+int bpt_profile_enable(int on) {
+    bpt::prof::clear();
+    bpt::prof::g_on = on != 0;
+    return BPT_OK;
+}
+
+int64_t bpt_profile_report(char* buf, size_t capacity) {
+    using namespace bpt::prof;
+    std::vector<std::pair<const char*, std::pair<int, double>>> agg;
+    for (Rec& r : g_recs) {
+        float ms = 0.f;
+        if (hipEventSynchronize(r.b) != hipSuccess || hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess) {
+            (void)hipGetLastError();
+            return -1;
+        }
+        bool found = false;
+        for (auto& e : agg)
+            if (e.first == r.name) {
+                e.second.first += 1;
+                e.second.second += ms;
+                found = true;
+            }
+        if (!found) agg.push_back({r.name, {1, (double)ms}});
+    }
+    std::string text;
+    for (auto& e : agg) {
+        char line[160];
+        snprintf(line, sizeof line, "%s %d %.6f\n", e.first, e.second.first, e.second.second);
+        text += line;
+    }
+    if (buf && capacity > 0) {
+        const size_t ncopy = std::min(capacity - 1, text.size());
+        memcpy(buf, text.data(), ncopy);
+        buf[ncopy] = 0;
+    }
+    return (int64_t)text.size() + 1;
+}
 
 void bpt_graph_destroy(bpt_graph_t* g) {
     if (!g) return;

@@ -86,6 +86,24 @@ struct bpt_graph {
     bpt::KeyTiles ktiles;
 };
 
+// Optional per-kernel timing: when enabled, every kernel launch of the library is
+// bracketed by two HIP events on the launch stream (see bpt_profile_enable).
+namespace bpt {
+namespace prof {
+bool enabled();
+void begin(const char* name, hipStream_t st);
+void end(hipStream_t st);
+}  // namespace prof
+}  // namespace bpt
+
+#define BPT_LAUNCH(name, kernel, grid, block, lds, st, ...)          \
+    do {                                                             \
+        const bool prof__ = bpt::prof::enabled();                    \
+        if (prof__) bpt::prof::begin(name, st);                      \
+        hipLaunchKernelGGL(kernel, grid, block, lds, st, __VA_ARGS__); \
+        if (prof__) bpt::prof::end(st);                              \
+    } while (0)
+
 #define BPT_HIP(expr)                                  \
     do {                                               \
         hipError_t e__ = (expr);                       \
