@@ -194,9 +194,8 @@ __device__ __forceinline__ Row<T> gather_row(rsrc_t r, int node, int row_bytes, 
     return out;
 }
 
-__device__ __forceinline__ uint32_t to_bf16_bits(float f) {  // round to nearest even
-    uint32_t u = __float_as_uint(f);
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+__device__ __forceinline__ uint32_t to_bf16_bits(float f) {  // round to nearest even (v_cvt_pk_bf16_f32)
+    return (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)f);
 }
 __device__ __forceinline__ void store8(float* p, const float (&x)[8]) {
     *reinterpret_cast<float4*>(p) = make_float4(x[0], x[1], x[2], x[3]);
@@ -1049,12 +1048,32 @@ __device__ __forceinline__ void wave_lds_sync() {  // order LDS traffic between 
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 __device__ __forceinline__ bf16x8_t as_bf16x8(const Row<bf16_t>& r) { return __builtin_bit_cast(bf16x8_t, r.w); }
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) { return to_bf16_bits(lo) | (to_bf16_bits(hi) << 16); }
+// two floats -> packed bf16 pair, round to nearest even (one v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    typedef __bf16 bf16x2v_t __attribute__((ext_vector_type(2)));
+    const bf16x2v_t v = {(__bf16)lo, (__bf16)hi};
+    return __builtin_bit_cast(uint32_t, v);
+}
 // two floats -> packed bf16 pair of their leading parts and packed bf16 pair of the remainders
 __device__ __forceinline__ void split_pack(float x, float y, uint32_t& hi, uint32_t& lo) {
-    const uint32_t xh = to_bf16_bits(x), yh = to_bf16_bits(y);
-    hi = xh | (yh << 16);
-    lo = pack_bf16(x - __uint_as_float(xh << 16), y - __uint_as_float(yh << 16));
+    hi = pack_bf16(x, y);
+    lo = pack_bf16(x - __uint_as_float(hi << 16), y - __uint_as_float(hi & 0xFFFF0000u));
+}
+// B operand of v_mfma_f32_16x16x32_bf16 out of rows staged in LDS: `rows` points at 32
+// staged rows (two chunks of 16) of `stride` bf16 each.  Lane (g, j) receives feature
+// 16f + j of rows 4g..4g+3 of the first chunk and of the second chunk -- the k order in
+// which the score tiles' C layout serves as the A operand.  ds_read_b64_tr_b16 reads,
+// per 16-lane group, a 4-row x 16-column block (lane 4r + c addresses columns 4c..4c+3
+// of row r) and hands lane i column i of the 4 rows.
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ bf16x8_t lds_transposed_b(const bf16_t* rows, int stride, int f, int g, int j) {
+    typedef __attribute__((address_space(3))) s16x4_t* lds_ptr_t;
+    const bf16_t* p = rows + (4 * g + (j >> 2)) * stride + 16 * f + 4 * (j & 3);
+    const s16x4_t x = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)p);
+    const s16x4_t y = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p + 16 * stride));
+    typedef short s16x8_t __attribute__((ext_vector_type(8)));
+    const s16x8_t xy = {x[0], x[1], x[2], x[3], y[0], y[1], y[2], y[3]};
+    return __builtin_bit_cast(bf16x8_t, xy);
 }
 
 __global__ void __launch_bounds__(kTileThreads) fwd_tile_kernel(const TileArgs a) {
@@ -1200,13 +1219,7 @@ __global__ void __launch_bounds__(kTileThreads) fwd_tile_kernel(const TileArgs a
 #pragma unroll
                     for (int f = 0; f < 4; ++f) {
                         // B[k][n]: column k of the pair (same interleaving as P), feature 16f + j
-                        const bf16_t* vc = v_s + 16 * f + j;
-                        u32x4 vb;
-                        vb.x = (uint32_t)vc[(4 * g + 0) * kVStride] | ((uint32_t)vc[(4 * g + 1) * kVStride] << 16);
-                        vb.y = (uint32_t)vc[(4 * g + 2) * kVStride] | ((uint32_t)vc[(4 * g + 3) * kVStride] << 16);
-                        vb.z = (uint32_t)vc[(16 + 4 * g + 0) * kVStride] | ((uint32_t)vc[(16 + 4 * g + 1) * kVStride] << 16);
-                        vb.w = (uint32_t)vc[(16 + 4 * g + 2) * kVStride] | ((uint32_t)vc[(16 + 4 * g + 3) * kVStride] << 16);
-                        o[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pA, __builtin_bit_cast(bf16x8_t, vb), o[f], 0, 0, 0);
+                        o[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pA, lds_transposed_b(v_s, kVStride, f, g, j), o[f], 0, 0, 0);
                     }
                 }
             }
@@ -1350,13 +1363,7 @@ __global__ void __launch_bounds__(kTileThreads) bwd_q_tile_kernel(const TileArgs
             const bf16x8_t pH = __builtin_bit_cast(bf16x8_t, ph), pL = __builtin_bit_cast(bf16x8_t, pl);
 #pragma unroll
             for (int f = 0; f < 4; ++f) {
-                const bf16_t* kc = k_s + 16 * f + j;
-                u32x4 kt;
-                kt.x = (uint32_t)kc[(4 * g + 0) * kVStride] | ((uint32_t)kc[(4 * g + 1) * kVStride] << 16);
-                kt.y = (uint32_t)kc[(4 * g + 2) * kVStride] | ((uint32_t)kc[(4 * g + 3) * kVStride] << 16);
-                kt.z = (uint32_t)kc[(16 + 4 * g + 0) * kVStride] | ((uint32_t)kc[(16 + 4 * g + 1) * kVStride] << 16);
-                kt.w = (uint32_t)kc[(16 + 4 * g + 2) * kVStride] | ((uint32_t)kc[(16 + 4 * g + 3) * kVStride] << 16);
-                const bf16x8_t kB = __builtin_bit_cast(bf16x8_t, kt);
+                const bf16x8_t kB = lds_transposed_b(k_s, kVStride, f, g, j);
                 ow[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wH, kB, ow[f], 0, 0, 0);
                 ow[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wL, kB, ow[f], 0, 0, 0);
                 op[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pH, kB, op[f], 0, 0, 0);
@@ -1537,18 +1544,7 @@ __global__ void __launch_bounds__(kTileThreads) bwd_kv_tile_kernel(const KeyArgs
             const bf16x8_t pH = __builtin_bit_cast(bf16x8_t, xph), pL = __builtin_bit_cast(bf16x8_t, xpl);
 #pragma unroll
             for (int f = 0; f < 4; ++f) {
-                const bf16_t* qc = q_s + 16 * f + j;
-                const bf16_t* gc = g_s + 16 * f + j;
-                u32x4 qt, gt;
-                qt.x = (uint32_t)qc[(4 * g + 0) * kVStride] | ((uint32_t)qc[(4 * g + 1) * kVStride] << 16);
-                qt.y = (uint32_t)qc[(4 * g + 2) * kVStride] | ((uint32_t)qc[(4 * g + 3) * kVStride] << 16);
-                qt.z = (uint32_t)qc[(16 + 4 * g + 0) * kVStride] | ((uint32_t)qc[(16 + 4 * g + 1) * kVStride] << 16);
-                qt.w = (uint32_t)qc[(16 + 4 * g + 2) * kVStride] | ((uint32_t)qc[(16 + 4 * g + 3) * kVStride] << 16);
-                gt.x = (uint32_t)gc[(4 * g + 0) * kVStride] | ((uint32_t)gc[(4 * g + 1) * kVStride] << 16);
-                gt.y = (uint32_t)gc[(4 * g + 2) * kVStride] | ((uint32_t)gc[(4 * g + 3) * kVStride] << 16);
-                gt.z = (uint32_t)gc[(16 + 4 * g + 0) * kVStride] | ((uint32_t)gc[(16 + 4 * g + 1) * kVStride] << 16);
-                gt.w = (uint32_t)gc[(16 + 4 * g + 2) * kVStride] | ((uint32_t)gc[(16 + 4 * g + 3) * kVStride] << 16);
-                const bf16x8_t qB = __builtin_bit_cast(bf16x8_t, qt), gB = __builtin_bit_cast(bf16x8_t, gt);
+                const bf16x8_t qB = lds_transposed_b(q_s, kVStride, f, g, j), gB = lds_transposed_b(g_s, kVStride, f, g, j);
                 dk[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sH, qB, dk[f], 0, 0, 0);
                 dk[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sL, qB, dk[f], 0, 0, 0);
                 dv[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pH, gB, dv[f], 0, 0, 0);
@@ -1670,14 +1666,20 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct DeviceLimits {
     int cus = 0;
-    size_t lds = 0;
+    size_t lds = 0;     // LDS one workgroup may use
+    size_t lds_cu = 0;  // LDS of one compute unit, shared by its resident workgroups
 };
 
 int device_limits(const bpt_graph* g, DeviceLimits* out) {
-    int lds = 0;
+    int lds = 0, lds_cu = 0;
     BPT_HIP(hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, g->device));
+    if (hipDeviceGetAttribute(&lds_cu, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, g->device) != hipSuccess) {
+        (void)hipGetLastError();
+        lds_cu = 0;
+    }
     out->cus = g->num_cus > 0 ? g->num_cus : 256;
     out->lds = lds > 0 ? (size_t)lds : 65536;
+    out->lds_cu = std::max<size_t>(out->lds, lds_cu > 0 ? (size_t)lds_cu : 0);
     return BPT_OK;
 }
 
@@ -1701,18 +1703,42 @@ int check_shape(const bpt_graph* g, const bpt_shape_t* s) {
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
-// Resident workgroups per CU for a persistent launch, from the runtime's occupancy
-// calculator; the grid is that times the CU count, rounded down to a multiple of 8
-// (one share of the tile space per XCD).
+// Workgroups of `kernel` one compute unit holds at once: the larger of the runtime's
+// occupancy figure and an estimate from the kernel's registers (512 per SIMD lane,
+// shared by at most 8 resident wavefronts per SIMD, 4 SIMDs) and the LDS of the whole
+// compute unit.  Over-estimating is harmless for a persistent launch: surplus
+// workgroups start when others finish and still take only their own share of the work.
+template <typename K>
+int resident_blocks(K kernel, int threads, size_t dyn_lds, const DeviceLimits& lim) {
+    int api = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&api, kernel, threads, dyn_lds) != hipSuccess) {
+        (void)hipGetLastError();
+        api = 0;
+    }
+    int est = 0;
+    hipFuncAttributes fa;
+    if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(kernel)) == hipSuccess) {
+        const int regs = std::max(8, (fa.numRegs + 7) / 8 * 8);
+        const int waves_per_simd = std::min(8, 512 / regs);
+        const int wg_waves_per_simd = (threads / 64 + 3) / 4;
+        const size_t lds = dyn_lds + fa.sharedSizeBytes;
+        est = waves_per_simd / wg_waves_per_simd;
+        if (lds > 0) est = std::min<int>(est, (int)(lim.lds_cu / lds));
+        est = std::min(est, 2048 / threads);
+    } else {
+        (void)hipGetLastError();
+    }
+    return std::max(1, std::max(api, est));
+}
+
+// Grid of a persistent launch: resident workgroups per compute unit times their number,
+// rounded down to a multiple of 8 (one share of the tile space per XCD).
 template <typename K>
 int persistent_grid(K kernel, int threads, size_t lds, const DeviceLimits& lim, int* grid) {
     if (lds > 65536)
         BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                     (int)lds));
-    int per_cu = 0;
-    BPT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, lds));
-    per_cu = std::max(1, per_cu);
-    *grid = std::max(8, lim.cus * per_cu / 8 * 8);
+    *grid = std::max(8, lim.cus * resident_blocks(kernel, threads, lds, lim) / 8 * 8);
     return BPT_OK;
 }
 
@@ -1765,9 +1791,7 @@ int launch_tiles(const char* name, K kernel, const TileArgs& t, const DeviceLimi
     if (lds > 65536)
         BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                     (int)lds));
-    int per_cu = 0;
-    BPT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kTileThreads, lds));
-    const int grid = std::max(8, lim.cus * std::max(1, per_cu) / 8 * 8);
+    const int grid = std::max(8, lim.cus * resident_blocks(kernel, kTileThreads, lds, lim) / 8 * 8);
     BPT_LAUNCH(name, kernel, dim3(grid), dim3(kTileThreads), lds, st, t);
     BPT_HIP(hipGetLastError());
     return BPT_OK;
@@ -1906,7 +1930,7 @@ int plan_bwd(const bpt_graph* g, const bpt_shape_t* s, BwdPlan* p) {
         p->drel_grid_y = (p->drel_rows + chunk - 1) / chunk;
         blocks = (int64_t)s->B * s->H * (g->n / p->drel_block);
     }
-    const int per_cu = (int)std::max<size_t>(1, std::min<size_t>(4, lim.lds / p->drel_lds));
+    const int per_cu = (int)std::max<size_t>(1, std::min<size_t>(4, lim.lds_cu / p->drel_lds));
     p->drel_grid_x = (int)std::max<int64_t>(1, std::min<int64_t>(blocks, (int64_t)lim.cus * per_cu / p->drel_grid_y));
     const size_t bh = (size_t)s->B * s->H;
     size_t off = 0;
@@ -2035,9 +2059,7 @@ int run_bwd_kv_tiles(const bpt_graph* g, const BwdPlan& p, const AttnArgs& a, co
     if (p.kv_lds > 65536)
         BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_kv_tile_kernel),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.kv_lds));
-    int per_cu = 0;
-    BPT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, bwd_kv_tile_kernel, kTileThreads, p.kv_lds));
-    const int grid = std::max(8, lim.cus * std::max(1, per_cu) / 8 * 8);
+    const int grid = std::max(8, lim.cus * resident_blocks(bwd_kv_tile_kernel, kTileThreads, p.kv_lds, lim) / 8 * 8);
     BPT_LAUNCH("bwd_kv_tile_kernel", bwd_kv_tile_kernel, dim3(grid), dim3(kTileThreads), p.kv_lds, st, t);
     BPT_HIP(hipGetLastError());
     if (kt.num_multi > 0) {
