@@ -1018,7 +1018,7 @@ constexpr int kTileThreads = 256;
 constexpr int kTileWaves = kTileThreads / 64;
 constexpr int kRelStride = 72;   // bf16 per LDS row of the compact table (64 + padding: 144 B)
 constexpr int kVStride = 68;     // bf16 per LDS row of a staged V row (136 B)
-constexpr int kGroup = 8;        // chunks per softmax group
+constexpr int kGroup = 4;        // chunks per softmax group
 
 struct TileArgs {
     const bf16_t *Q, *K, *V, *rel;
@@ -1029,7 +1029,7 @@ struct TileArgs {
     float scale;
     const int32_t *chunk_ptr, *cols, *cid_to_id;
     const int16_t* map;
-    int32_t num_tiles, num_cids, cid_pad, bias_stride;
+    int32_t num_tiles, num_chunks, num_cids, cid_pad, bias_stride;
     int32_t row_bytes;
     uint32_t slab_bytes;
     // backward, query side
@@ -1097,6 +1097,8 @@ __global__ void __launch_bounds__(kTileThreads) fwd_tile_kernel(const TileArgs a
     __syncthreads();
 
     const float qscale = a.scale * kLog2e;
+    const rsrc_t rC = make_rsrc(a.cols, (uint32_t)a.num_chunks * 64u);   // [chunks][16] int32
+    const rsrc_t rM = make_rsrc(a.map, (uint32_t)a.num_chunks * 512u);   // [chunks][16][16] int16
     const int groups_per_bh = (a.num_tiles + kTileWaves - 1) / kTileWaves;
     for (TileWalk w(a.BH * groups_per_bh); w.t < w.t_end; w.t += w.step) {
         const int bh = w.t / groups_per_bh;
@@ -1129,38 +1131,59 @@ __global__ void __launch_bounds__(kTileThreads) fwd_tile_kernel(const TileArgs a
         for (int f = 0; f < 4; ++f) o[f] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
         for (int grp = 0; grp < nch; grp += kGroup) {
-            // scores of up to 8 chunks
+            // Straight-line loads: the column ids and map words of the whole group, then all K
+            // rows, then all V rows.  A chunk past the end of the tile repeats the last chunk
+            // (valid addresses) with every column masked, so nothing here branches.
             float sc[kGroup][4];
-            Row<bf16_t> ka[kGroup], kb[kGroup];
+            Row<bf16_t> ka[kGroup], kb[kGroup], va[kGroup], vb[kGroup];
+            int off[kGroup];
             uint2 mp[kGroup];
 #pragma unroll
+            for (int ci = 0; ci < kGroup; ++ci) {
+                const int at = (cp0 + min(grp + ci, nch - 1)) * 16 + j;
+                off[ci] = buf_i32(rC, at * 4);
+                const u32x2 m2 = __builtin_amdgcn_raw_buffer_load_b64(rM, at * 32 + 8 * g, 0, 0);
+                const bool live = grp + ci < nch;
+                mp[ci] = make_uint2(live ? m2.x : ~0u, live ? m2.y : ~0u);
+            }
+#pragma unroll
+            for (int ci = 0; ci < kGroup; ++ci) {
+                off[ci] = (int)__umul24(off[ci], a.row_bytes) + feat_off;
+                buf_row(rK, off[ci], ka[ci]);
+                buf_row(rK, off[ci] + 16, kb[ci]);
+            }
+#pragma unroll
+            for (int ci = 0; ci < kGroup; ++ci) {
+                buf_row(rV, off[ci], va[ci]);
+                buf_row(rV, off[ci] + 16, vb[ci]);
+            }
+            __builtin_amdgcn_sched_barrier(0);  // all of the group's row loads are in flight before any use
+            // the relative-position terms of the group's 16 elements, read unconditionally
+            int cid[kGroup][4];
+            float bv[kGroup][4];
+#pragma unroll
+            for (int ci = 0; ci < kGroup; ++ci) {
+                cid[ci][0] = (int)(short)(mp[ci].x & 0xFFFFu);
+                cid[ci][1] = (int)(short)(mp[ci].x >> 16);
+                cid[ci][2] = (int)(short)(mp[ci].y & 0xFFFFu);
+                cid[ci][3] = (int)(short)(mp[ci].y >> 16);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) bv[ci][r] = bias_s[j * a.bias_stride + max(cid[ci][r], 0)];
+            }
+#pragma unroll
             for (int ci = 0; ci < kGroup; ++ci)
-                if (grp + ci < nch) {
-                    const int at = (cp0 + grp + ci) * 16 + j;
-                    const int node = a.cols[at];
-                    const int off = (int)__umul24(node, a.row_bytes) + feat_off;
-                    buf_row(rK, off, ka[ci]);
-                    buf_row(rK, off + 16, kb[ci]);
-                    mp[ci] = *reinterpret_cast<const uint2*>(a.map + (int64_t)at * 16 + 4 * g);
-                }
+#pragma unroll
+                for (int r = 0; r < 4; ++r) asm volatile("" : "+v"(bv[ci][r]));  // keeps the reads out of branches on the mask
             float gm = kNegBig;
 #pragma unroll
             for (int ci = 0; ci < kGroup; ++ci) {
-                if (grp + ci < nch) {
-                    f32x4_t s4 = {0.f, 0.f, 0.f, 0.f};
-                    s4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ka[ci]), qb0, s4, 0, 0, 0);
-                    s4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kb[ci]), qb1, s4, 0, 0, 0);
-                    const int cid[4] = {(int)(short)(mp[ci].x & 0xFFFFu), (int)(short)(mp[ci].x >> 16),
-                                        (int)(short)(mp[ci].y & 0xFFFFu), (int)(short)(mp[ci].y >> 16)};
+                f32x4_t s4 = {0.f, 0.f, 0.f, 0.f};
+                s4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ka[ci]), qb0, s4, 0, 0, 0);
+                s4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kb[ci]), qb1, s4, 0, 0, 0);
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const float b = bias_s[j * a.bias_stride + max(cid[r], 0)];
-                        sc[ci][r] = cid[r] >= 0 ? (s4[r] + b) * qscale : kNegBig;
-                        gm = fmaxf(gm, sc[ci][r]);
-                    }
-                } else {
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) sc[ci][r] = kNegBig;
+                for (int r = 0; r < 4; ++r) {
+                    sc[ci][r] = cid[ci][r] >= 0 ? (s4[r] + bv[ci][r]) * qscale : kNegBig;
+                    gm = fmaxf(gm, sc[ci][r]);
                 }
             }
             gm = fmaxf(gm, __shfl_xor(gm, 16));
@@ -1189,15 +1212,7 @@ __global__ void __launch_bounds__(kTileThreads) fwd_tile_kernel(const TileArgs a
 #pragma unroll
             for (int pi = 0; pi < kGroup / 2; ++pi) {
                 if (grp + 2 * pi < nch) {
-                    const int at = (cp0 + grp + 2 * pi) * 16 + j;
-                    const int n0 = a.cols[at], n1 = a.cols[at + 16];
-                    Row<bf16_t> v00, v01, v10, v11;
-                    const int off0 = (int)__umul24(n0, a.row_bytes) + feat_off;
-                    const int off1 = (int)__umul24(n1, a.row_bytes) + feat_off;
-                    buf_row(rV, off0, v00);
-                    buf_row(rV, off0 + 16, v01);
-                    buf_row(rV, off1, v10);
-                    buf_row(rV, off1 + 16, v11);
+                    const Row<bf16_t> v00 = va[2 * pi], v01 = vb[2 * pi], v10 = va[2 * pi + 1], v11 = vb[2 * pi + 1];
                     wave_lds_sync();  // the previous pair's reads of v_s are done
                     uint2* d0 = reinterpret_cast<uint2*>(v_s + j * kVStride + 16 * g);
                     uint2* d1 = reinterpret_cast<uint2*>(v_s + (16 + j) * kVStride + 16 * g);
@@ -1267,6 +1282,9 @@ __global__ void __launch_bounds__(kTileThreads) bwd_q_tile_kernel(const TileArgs
     __syncthreads();
 
     const float qscale = a.scale * kLog2e;
+    const rsrc_t rC = make_rsrc(a.cols, (uint32_t)a.num_chunks * 64u);
+    const rsrc_t rM = make_rsrc(a.map, (uint32_t)a.num_chunks * 512u);
+    const rsrc_t rE = make_rsrc(a.emap, (uint32_t)a.num_chunks * 512u);
     const int groups_per_bh = (a.num_tiles + kTileWaves - 1) / kTileWaves;
     for (TileWalk w(a.BH * groups_per_bh); w.t < w.t_end; w.t += w.step) {
         const int bh = w.t / groups_per_bh;
@@ -1285,7 +1303,8 @@ __global__ void __launch_bounds__(kTileThreads) bwd_q_tile_kernel(const TileArgs
         const bf16x8_t gb0 = *reinterpret_cast<const bf16x8_t*>(grow);
         const bf16x8_t gb1 = *reinterpret_cast<const bf16x8_t*>(grow + 8);
         const float lse2 = a.lse_r[(int64_t)bh * a.N + t0 + j] * kLog2e;
-        float2* wp_row = a.wp + (int64_t)bh * a.e_tok + a.row_ptr[t0 + j];
+        const rsrc_t rW = make_rsrc(a.wp + (int64_t)bh * a.e_tok, (uint32_t)a.e_tok * 8u);
+        const int wp0 = a.row_ptr[t0 + j];  // first edge of this lane's token row
 
         for (int c = 0; c < a.cid_pad; c += 16) {
             const bf16_t* rrow = rel_s + (c + j) * kRelStride + 16 * g;
@@ -1301,73 +1320,102 @@ __global__ void __launch_bounds__(kTileThreads) bwd_q_tile_kernel(const TileArgs
 #pragma unroll
         for (int f = 0; f < 4; ++f) ow[f] = op[f] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-        for (int c2 = 0; c2 < nch; c2 += 2) {
-            float pw[2][4], pp[2][4];
-            Row<bf16_t> ka[2], kb[2], va[2], vb[2];
-            uint2 mp[2], ep[2];
+        for (int grp = 0; grp < nch; grp += kGroup) {
+            // straight-line loads of the whole group (see fwd_tile_kernel): ids, then K and V rows
+            Row<bf16_t> ka[kGroup], kb[kGroup], va[kGroup], vb[kGroup];
+            int off[kGroup];
+            uint2 mp[kGroup], ep[kGroup];
 #pragma unroll
-            for (int ci = 0; ci < 2; ++ci) {
-                const int at = (cp0 + c2 + ci) * 16 + j;
-                const int off = (int)__umul24(a.cols[at], a.row_bytes) + feat_off;
-                buf_row(rK, off, ka[ci]);
-                buf_row(rK, off + 16, kb[ci]);
-                buf_row(rV, off, va[ci]);
-                buf_row(rV, off + 16, vb[ci]);
-                mp[ci] = *reinterpret_cast<const uint2*>(a.map + (int64_t)at * 16 + 4 * g);
-                ep[ci] = *reinterpret_cast<const uint2*>(a.emap + (int64_t)at * 16 + 4 * g);
+            for (int ci = 0; ci < kGroup; ++ci) {
+                const int at = (cp0 + min(grp + ci, nch - 1)) * 16 + j;
+                off[ci] = buf_i32(rC, at * 4);
+                const u32x2 m2 = __builtin_amdgcn_raw_buffer_load_b64(rM, at * 32 + 8 * g, 0, 0);
+                const u32x2 e2 = __builtin_amdgcn_raw_buffer_load_b64(rE, at * 32 + 8 * g, 0, 0);
+                const bool live = grp + ci < nch;
+                mp[ci] = make_uint2(live ? m2.x : ~0u, live ? m2.y : ~0u);
+                ep[ci] = make_uint2(e2.x, e2.y);
             }
-            wave_lds_sync();  // the previous pair's reads of k_s are done
 #pragma unroll
-            for (int ci = 0; ci < 2; ++ci) {
-                f32x4_t s4 = {0.f, 0.f, 0.f, 0.f}, d4 = {0.f, 0.f, 0.f, 0.f};
-                s4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ka[ci]), qb0, s4, 0, 0, 0);
-                s4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kb[ci]), qb1, s4, 0, 0, 0);
-                d4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(va[ci]), gb0, d4, 0, 0, 0);
-                d4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vb[ci]), gb1, d4, 0, 0, 0);
-                const int cid[4] = {(int)(short)(mp[ci].x & 0xFFFFu), (int)(short)(mp[ci].x >> 16),
-                                    (int)(short)(mp[ci].y & 0xFFFFu), (int)(short)(mp[ci].y >> 16)};
-                const int eo[4] = {(int)(ep[ci].x & 0xFFFFu), (int)(ep[ci].x >> 16), (int)(ep[ci].y & 0xFFFFu),
-                                   (int)(ep[ci].y >> 16)};
+            for (int ci = 0; ci < kGroup; ++ci) {
+                off[ci] = (int)__umul24(off[ci], a.row_bytes) + feat_off;
+                buf_row(rK, off[ci], ka[ci]);
+                buf_row(rK, off[ci] + 16, kb[ci]);
+                buf_row(rV, off[ci], va[ci]);
+                buf_row(rV, off[ci] + 16, vb[ci]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            int cid[kGroup][4];
+            float bv[kGroup][4];
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const bool valid = cid[r] >= 0;
-                    const float b = bias_s[j * a.bias_stride + max(cid[r], 0)];
-                    const float p = valid ? fast_exp2((s4[r] + b) * qscale - lse2) : 0.f;
-                    const float wgt = p * d4[r];
-                    dl_part += wgt;
-                    pw[ci][r] = wgt;
-                    pp[ci][r] = p;
-                    if (valid) wp_row[eo[r]] = make_float2(wgt, p);
+            for (int ci = 0; ci < kGroup; ++ci) {
+                cid[ci][0] = (int)(short)(mp[ci].x & 0xFFFFu);
+                cid[ci][1] = (int)(short)(mp[ci].x >> 16);
+                cid[ci][2] = (int)(short)(mp[ci].y & 0xFFFFu);
+                cid[ci][3] = (int)(short)(mp[ci].y >> 16);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) bv[ci][r] = bias_s[j * a.bias_stride + max(cid[ci][r], 0)];
+            }
+#pragma unroll
+            for (int ci = 0; ci < kGroup; ++ci)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) asm volatile("" : "+v"(bv[ci][r]));  // reads stay out of branches on the mask
+#pragma unroll
+            for (int pi = 0; pi < kGroup / 2; ++pi) {
+                if (grp + 2 * pi >= nch) break;  // wave-uniform
+                float pw[2][4], pp[2][4];
+                wave_lds_sync();  // the previous pair's reads of k_s are done
+#pragma unroll
+                for (int c = 0; c < 2; ++c) {
+                    const int ci = 2 * pi + c;
+                    f32x4_t s4 = {0.f, 0.f, 0.f, 0.f}, d4 = {0.f, 0.f, 0.f, 0.f};
+                    s4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ka[ci]), qb0, s4, 0, 0, 0);
+                    s4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kb[ci]), qb1, s4, 0, 0, 0);
+                    d4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(va[ci]), gb0, d4, 0, 0, 0);
+                    d4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vb[ci]), gb1, d4, 0, 0, 0);
+                    const int eo[4] = {(int)(ep[ci].x & 0xFFFFu), (int)(ep[ci].x >> 16), (int)(ep[ci].y & 0xFFFFu),
+                                       (int)(ep[ci].y >> 16)};
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const bool valid = cid[ci][r] >= 0;
+                        const float p = valid ? fast_exp2((s4[r] + bv[ci][r]) * qscale - lse2) : 0.f;
+                        const float wgt = p * d4[r];
+                        dl_part += wgt;
+                        pw[c][r] = wgt;
+                        pp[c][r] = p;
+                        // a masked element's store gets an offset past the buffer and is dropped
+                        const u32x2 val = {__float_as_uint(wgt), __float_as_uint(p)};
+                        __builtin_amdgcn_raw_buffer_store_b64(val, rW, valid ? (wp0 + eo[r]) * 8 : -1, 0, 0);
+                    }
+                    // stage the chunk's K rows as the B operand of the second product
+                    uint2* d = reinterpret_cast<uint2*>(k_s + (16 * c + j) * kVStride + 16 * g);
+                    d[0] = make_uint2(ka[ci].w.x, ka[ci].w.y);
+                    d[1] = make_uint2(ka[ci].w.z, ka[ci].w.w);
+                    d[2] = make_uint2(kb[ci].w.x, kb[ci].w.y);
+                    d[3] = make_uint2(kb[ci].w.z, kb[ci].w.w);
                 }
-                // stage the chunk's K rows as the B operand of the second product
-                uint2* d = reinterpret_cast<uint2*>(k_s + (16 * ci + j) * kVStride + 16 * g);
-                d[0] = make_uint2(ka[ci].w.x, ka[ci].w.y);
-                d[1] = make_uint2(ka[ci].w.z, ka[ci].w.w);
-                d[2] = make_uint2(kb[ci].w.x, kb[ci].w.y);
-                d[3] = make_uint2(kb[ci].w.z, kb[ci].w.w);
-            }
-            wave_lds_sync();
-            // W and P as A operands, each split into bf16 hi + lo: A - delta*Bv cancels when a
-            // row's softmax is peaked, so the two products need more than 8 mantissa bits
-            uint32_t whi[4], wlo[4], phi[4], plo[4];
+                wave_lds_sync();
+                // W and P as A operands, each split into bf16 hi + lo: A - delta*Bv cancels when a
+                // row's softmax is peaked, so the two products need more than 8 mantissa bits
+                uint32_t whi[4], wlo[4], phi[4], plo[4];
 #pragma unroll
-            for (int ci = 0; ci < 2; ++ci) {
-                split_pack(pw[ci][0], pw[ci][1], whi[2 * ci], wlo[2 * ci]);
-                split_pack(pw[ci][2], pw[ci][3], whi[2 * ci + 1], wlo[2 * ci + 1]);
-                split_pack(pp[ci][0], pp[ci][1], phi[2 * ci], plo[2 * ci]);
-                split_pack(pp[ci][2], pp[ci][3], phi[2 * ci + 1], plo[2 * ci + 1]);
-            }
-            const u32x4 wh = {whi[0], whi[1], whi[2], whi[3]}, wl = {wlo[0], wlo[1], wlo[2], wlo[3]};
-            const u32x4 ph = {phi[0], phi[1], phi[2], phi[3]}, pl = {plo[0], plo[1], plo[2], plo[3]};
-            const bf16x8_t wH = __builtin_bit_cast(bf16x8_t, wh), wL = __builtin_bit_cast(bf16x8_t, wl);
-            const bf16x8_t pH = __builtin_bit_cast(bf16x8_t, ph), pL = __builtin_bit_cast(bf16x8_t, pl);
+                for (int c = 0; c < 2; ++c) {
+                    split_pack(pw[c][0], pw[c][1], whi[2 * c], wlo[2 * c]);
+                    split_pack(pw[c][2], pw[c][3], whi[2 * c + 1], wlo[2 * c + 1]);
+                    split_pack(pp[c][0], pp[c][1], phi[2 * c], plo[2 * c]);
+                    split_pack(pp[c][2], pp[c][3], phi[2 * c + 1], plo[2 * c + 1]);
+                }
+                const u32x4 wh = {whi[0], whi[1], whi[2], whi[3]}, wl = {wlo[0], wlo[1], wlo[2], wlo[3]};
+                const u32x4 ph = {phi[0], phi[1], phi[2], phi[3]}, pl = {plo[0], plo[1], plo[2], plo[3]};
+                const bf16x8_t wH = __builtin_bit_cast(bf16x8_t, wh), wL = __builtin_bit_cast(bf16x8_t, wl);
+                const bf16x8_t pH = __builtin_bit_cast(bf16x8_t, ph), pL = __builtin_bit_cast(bf16x8_t, pl);
 #pragma unroll
-            for (int f = 0; f < 4; ++f) {
-                const bf16x8_t kB = lds_transposed_b(k_s, kVStride, f, g, j);
-                ow[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wH, kB, ow[f], 0, 0, 0);
-                ow[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wL, kB, ow[f], 0, 0, 0);
-                op[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pH, kB, op[f], 0, 0, 0);
-                op[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pL, kB, op[f], 0, 0, 0);
+                for (int f = 0; f < 4; ++f) {
+                    const bf16x8_t kB = lds_transposed_b(k_s, kVStride, f, g, j);
+                    ow[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wH, kB, ow[f], 0, 0, 0);
+                    ow[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wL, kB, ow[f], 0, 0, 0);
+                    op[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pH, kB, op[f], 0, 0, 0);
+                    op[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pL, kB, op[f], 0, 0, 0);
+                }
             }
         }
         float delta = dl_part + __shfl_xor(dl_part, 16);
@@ -1515,19 +1563,29 @@ __global__ void __launch_bounds__(kTileThreads) bwd_kv_tile_kernel(const KeyArgs
                 dg[3] = make_uint2(ga[ci][1].w.z, ga[ci][1].w.w);
             }
             wave_lds_sync();
-            float ds[2][4], pp[2][4];
+            float ds[2][4], pp[2][4], bv[2][4];
+            int bid[2][4];
 #pragma unroll
             for (int ci = 0; ci < 2; ++ci) {
-                const int bid[4] = {(int)(short)(mp[ci].x & 0xFFFFu), (int)(short)(mp[ci].x >> 16),
-                                    (int)(short)(mp[ci].y & 0xFFFFu), (int)(short)(mp[ci].y >> 16)};
+                bid[ci][0] = (int)(short)(mp[ci].x & 0xFFFFu);
+                bid[ci][1] = (int)(short)(mp[ci].x >> 16);
+                bid[ci][2] = (int)(short)(mp[ci].y & 0xFFFFu);
+                bid[ci][3] = (int)(short)(mp[ci].y >> 16);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) bv[ci][r] = bias_s[(16 * ci + 4 * g + r) * bstride + max(bid[ci][r], 0)];
+            }
+#pragma unroll
+            for (int ci = 0; ci < 2; ++ci)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) asm volatile("" : "+v"(bv[ci][r]));  // reads stay out of branches on the mask
+#pragma unroll
+            for (int ci = 0; ci < 2; ++ci)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const float b = bias_s[(16 * ci + 4 * g + r) * bstride + max(bid[r], 0)];
-                    const float p = bid[r] >= 0 ? fast_exp2((s4[ci][r] + b) * qscale - st[ci][r].x) : 0.f;
+                    const float p = bid[ci][r] >= 0 ? fast_exp2((s4[ci][r] + bv[ci][r]) * qscale - st[ci][r].x) : 0.f;
                     pp[ci][r] = p;
                     ds[ci][r] = p * (d4[ci][r] - st[ci][r].y);
                 }
-            }
             // dS and P as A operands, each as bf16 hi + lo: the sums run over up to thousands of
             // queries and the tolerance is absolute, so 8 mantissa bits are not enough
             uint32_t shi[4], slo[4], phi[4], plo[4];
@@ -1833,6 +1891,7 @@ void fill_tile_args(TileArgs& t, const bpt_graph* g, const AttnArgs& a, int cid_
     t.cid_to_id = g->tiles.cid_to_id;
     t.map = g->tiles.map;
     t.num_tiles = g->tiles.num_tiles;
+    t.num_chunks = g->tiles.num_chunks;
     t.num_cids = g->tiles.num_cids;
     t.cid_pad = cid_pad;
     t.bias_stride = bias_stride;

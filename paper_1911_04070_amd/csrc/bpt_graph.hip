@@ -501,6 +501,7 @@ int make_token_tiles(int32_t n, int32_t k, int32_t num_levels, const std::vector
         chunk_ptr.push_back((int32_t)(cols.size() / 16));
     }
     out.num_cids = (int32_t)cid_to_id.size();
+    out.num_chunks = chunk_ptr.back();
     int rc;
     if ((rc = upload(chunk_ptr, &out.chunk_ptr)) || (rc = upload(cols, &out.cols)) || (rc = upload(map, &out.map)) ||
         (rc = upload(emap, &out.emap)) || (rc = upload(cid_to_id, &out.cid_to_id)))

@@ -36,6 +36,7 @@ struct Schedule {
 // padding slots repeat a real node and are masked).
 struct TokenTiles {
     int32_t num_tiles = 0;   // n / 16; 0 when the tile path is not built
+    int32_t num_chunks = 0;  // chunks of all tiles together
     int32_t num_cids = 0;    // relative-position ids used by token rows (compact numbering)
     int32_t* chunk_ptr = nullptr;  // [num_tiles+1] first chunk of a tile
     int32_t* cols = nullptr;       // [chunks][16] node id of a column
