@@ -1018,6 +1018,7 @@ constexpr int kTileThreads = 256;
 constexpr int kTileWaves = kTileThreads / 64;
 constexpr int kRelStride = 72;   // bf16 per LDS row of the compact table (64 + padding: 144 B)
 constexpr int kVStride = 68;     // bf16 per LDS row of a staged V row (136 B)
+constexpr int kRowStride = 72;   // bf16 per LDS row where rows are written and read 16 bytes at a time (144 B)
 constexpr int kGroup = 4;        // chunks per softmax group
 
 struct TileArgs {
@@ -1931,22 +1932,28 @@ struct KeyArgs {
     uint32_t slab_bytes;
     const int32_t *tile_node0, *tile_info, *cols, *task_tile, *task_c0, *task_nch, *task_part;
     const int16_t* map;
-    int32_t num_tasks, num_part, nb_pad, W, zero;
+    int32_t num_tasks, num_part, num_chunks, nb_pad, W, zero;
 };
 
-__global__ void __launch_bounds__(kTileThreads) bwd_kv_tile_kernel(const KeyArgs a) {
+template <int NBC>
+__global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int g = lane >> 4, j = lane & 15;
+    const int r8 = lane >> 3, piece = lane & 7;   // coalesced row fetches: row of the instruction, 16-byte piece
     const int bstride = a.nb_pad + 1;
     float* bias_s = reinterpret_cast<float*>(smem) + (size_t)wave * 32 * bstride;               // [32 queries][ids]
     bf16_t* q_s = reinterpret_cast<bf16_t*>(smem + (size_t)kTileWaves * 32 * bstride * sizeof(float)) +
-                  (size_t)wave * 64 * kVStride;                                                  // [32 queries][kVStride]
-    bf16_t* g_s = q_s + 32 * kVStride;
+                  (size_t)wave * 64 * kRowStride;                                                // [32 queries][kRowStride]
+    bf16_t* g_s = q_s + 32 * kRowStride;
+    float2* stat_s = reinterpret_cast<float2*>(smem + (size_t)kTileWaves * (32 * bstride * sizeof(float) +
+                                                                            64 * kRowStride * sizeof(bf16_t))) +
+                     (size_t)wave * 32;                                                          // [32 queries] (lse, delta)
     const float qscale = a.scale * kLog2e;
-    const int nbc = a.nb_pad >> 4;
     const int groups = (a.num_tasks + kTileWaves - 1) / kTileWaves;
+    const rsrc_t rC = make_rsrc(a.cols, (uint32_t)a.num_chunks * 64u);    // [chunks][16] int32
+    const rsrc_t rM = make_rsrc(a.map, (uint32_t)a.num_chunks * 512u);    // [chunks][16][16] int16
 
     for (TileWalk w(a.BH * groups); w.t < w.t_end; w.t += w.step) {
         const int bh = w.t / groups;
@@ -1958,7 +1965,41 @@ __global__ void __launch_bounds__(kTileThreads) bwd_kv_tile_kernel(const KeyArgs
         const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
         const rsrc_t rQ = make_rsrc(a.Q + base, a.slab_bytes), rG = make_rsrc(a.dout + base, a.slab_bytes);
         const rsrc_t rS = make_rsrc(a.stat + (int64_t)bh * a.N, (uint32_t)a.N * 8u);
-        const int feat_off = 16 * g * (int)sizeof(bf16_t);
+
+        // Software pipeline over pairs of chunks.  `Idx` = what has to be known before a pair's
+        // rows can be requested (its column ids and map words); the rows of pair i+1 are
+        // requested in the middle of pair i, as soon as the registers of pair i's rows are free,
+        // and the ids of pair i+2 right after, so the gathers overlap the second products.
+        int node[2][2];   // [chunk][half]: query node whose row this lane helps to fetch
+        uint2 mpn[2];
+        auto load_idx = [&](int c2) {   // a pair past the end repeats the last one (valid addresses, results unused)
+            const int cc = c0 + min(c2, nch - 2);
+#pragma unroll
+            for (int ci = 0; ci < 2; ++ci) {
+                const int at = (cc + ci) * 16;
+                node[ci][0] = buf_i32(rC, (at + r8) * 4);
+                node[ci][1] = buf_i32(rC, (at + 8 + r8) * 4);
+                const u32x2 m2 = __builtin_amdgcn_raw_buffer_load_b64(rM, (at + j) * 32 + 8 * g, 0, 0);
+                mpn[ci] = make_uint2(m2.x, m2.y);
+            }
+        };
+        // Row fetches are coalesced: 8 consecutive lanes take the 8 16-byte pieces of one row, an
+        // instruction fetches 8 whole rows (two per 16-row chunk).  The rows go through LDS to get
+        // into the operand layouts of the matrix instructions.
+        Row<bf16_t> qa[2][2], ga[2][2];
+        float2 stn[2][2];   // (lse, delta) of the row, kept by the lane that fetches its first piece
+        auto load_rows = [&]() {
+#pragma unroll
+            for (int ci = 0; ci < 2; ++ci)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int off = (int)__umul24(node[ci][h], a.row_bytes) + piece * 16;
+                    buf_row(rQ, off, qa[ci][h]);
+                    buf_row(rG, off, ga[ci][h]);
+                    stn[ci][h] = buf_f2(rS, node[ci][h] * 8);
+                }
+        };
+        load_idx(0);
 
         // B operands: the tile's keys (lane j <-> key j) and the rows of the table this level can meet
         const int64_t krow = base + (int64_t)(node0 + min(j, nkeys - 1)) * a.sn + 16 * g;
@@ -1966,84 +2007,87 @@ __global__ void __launch_bounds__(kTileThreads) bwd_kv_tile_kernel(const KeyArgs
         const bf16x8_t kb1 = *reinterpret_cast<const bf16x8_t*>(a.K + krow + 8);
         const bf16x8_t vb0 = *reinterpret_cast<const bf16x8_t*>(a.V + krow);
         const bf16x8_t vb1 = *reinterpret_cast<const bf16x8_t*>(a.V + krow + 8);
-        bf16x8_t rb[kMaxBiasChunks][2];
+        bf16x8_t rb[NBC][2];
 #pragma unroll
-        for (int bc = 0; bc < kMaxBiasChunks; ++bc)
-            if (bc < nbc) {
-                const int bid = 16 * bc + j;
-                int row = 0;
-                if (bid < a.W)
-                    row = level * a.W + bid;                        // (level, order)
-                else if (bid - a.W + 1 < a.num_levels)
-                    row = (bid - a.W + 1) * a.W + a.zero;            // r_anc of the ancestor's level
-                const bf16_t* rr = a.rel + (int64_t)row * kD + 16 * g;
-                rb[bc][0] = *reinterpret_cast<const bf16x8_t*>(rr);
-                rb[bc][1] = *reinterpret_cast<const bf16x8_t*>(rr + 8);
-            }
+        for (int bc = 0; bc < NBC; ++bc) {
+            const int bid = 16 * bc + j;
+            int row = 0;
+            if (bid < a.W)
+                row = level * a.W + bid;                        // (level, order)
+            else if (bid - a.W + 1 < a.num_levels)
+                row = (bid - a.W + 1) * a.W + a.zero;            // r_anc of the ancestor's level
+            const bf16_t* rr = a.rel + (int64_t)row * kD + 16 * g;
+            rb[bc][0] = *reinterpret_cast<const bf16x8_t*>(rr);
+            rb[bc][1] = *reinterpret_cast<const bf16x8_t*>(rr + 8);
+        }
+        load_rows();     // pair 0 (waits for its ids)
+        uint2 mp[2] = {mpn[0], mpn[1]};
+        load_idx(2);     // ids of pair 1
 
         f32x4_t dk[4], dv[4];
 #pragma unroll
         for (int f = 0; f < 4; ++f) dk[f] = dv[f] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
         for (int c2 = 0; c2 < nch; c2 += 2) {
-            Row<bf16_t> qa[2][2], ga[2][2];
-            float2 st[2][4];
-            uint2 mp[2];
-#pragma unroll
-            for (int ci = 0; ci < 2; ++ci) {
-                const int at = (c0 + c2 + ci) * 16;
-                const int off = (int)__umul24(a.cols[at + j], a.row_bytes) + feat_off;
-                buf_row(rQ, off, qa[ci][0]);
-                buf_row(rQ, off + 16, qa[ci][1]);
-                buf_row(rG, off, ga[ci][0]);
-                buf_row(rG, off + 16, ga[ci][1]);
-                const int4 u4 = *reinterpret_cast<const int4*>(a.cols + at + 4 * g);
-                st[ci][0] = buf_f2(rS, u4.x * 8);
-                st[ci][1] = buf_f2(rS, u4.y * 8);
-                st[ci][2] = buf_f2(rS, u4.z * 8);
-                st[ci][3] = buf_f2(rS, u4.w * 8);
-                mp[ci] = *reinterpret_cast<const uint2*>(a.map + ((int64_t)(c0 + c2 + ci) * 16 + j) * 16 + 4 * g);
-            }
             wave_lds_sync();  // the previous pair's LDS reads are done
+#pragma unroll
+            for (int ci = 0; ci < 2; ++ci)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int row = 16 * ci + 8 * h + r8;
+                    *reinterpret_cast<uint4*>(q_s + row * kRowStride + piece * 8) = qa[ci][h].w;
+                    *reinterpret_cast<uint4*>(g_s + row * kRowStride + piece * 8) = ga[ci][h].w;
+                    if (piece == 0) stat_s[row] = stn[ci][h];
+                }
+            __builtin_amdgcn_sched_barrier(0);
+            // the row registers are free: request the next pair's rows, then the ids of the pair after it
+            const uint2 mpc[2] = {mp[0], mp[1]};
+            load_rows();
+            mp[0] = mpn[0];
+            mp[1] = mpn[1];
+            load_idx(c2 + 4);
+            __builtin_amdgcn_sched_barrier(0);
+            wave_lds_sync();
             f32x4_t s4[2], d4[2];
 #pragma unroll
             for (int ci = 0; ci < 2; ++ci) {
-                const bf16x8_t q0 = as_bf16x8(qa[ci][0]), q1 = as_bf16x8(qa[ci][1]);
+                const bf16_t* qr = q_s + (16 * ci + j) * kRowStride + 16 * g;
+                const bf16_t* gr = g_s + (16 * ci + j) * kRowStride + 16 * g;
+                const bf16x8_t q0 = *reinterpret_cast<const bf16x8_t*>(qr), q1 = *reinterpret_cast<const bf16x8_t*>(qr + 8);
+                const bf16x8_t g0 = *reinterpret_cast<const bf16x8_t*>(gr), g1 = *reinterpret_cast<const bf16x8_t*>(gr + 8);
                 s4[ci] = d4[ci] = f32x4_t{0.f, 0.f, 0.f, 0.f};
                 s4[ci] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(q0, kb0, s4[ci], 0, 0, 0);
                 s4[ci] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(q1, kb1, s4[ci], 0, 0, 0);
-                d4[ci] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ga[ci][0]), vb0, d4[ci], 0, 0, 0);
-                d4[ci] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ga[ci][1]), vb1, d4[ci], 0, 0, 0);
+                d4[ci] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(g0, vb0, d4[ci], 0, 0, 0);
+                d4[ci] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(g1, vb1, d4[ci], 0, 0, 0);
 #pragma unroll
-                for (int bc = 0; bc < kMaxBiasChunks; ++bc)
-                    if (bc < nbc) {
-                        f32x4_t b4 = {0.f, 0.f, 0.f, 0.f};
-                        b4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(q0, rb[bc][0], b4, 0, 0, 0);
-                        b4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(q1, rb[bc][1], b4, 0, 0, 0);
+                for (int bc = 0; bc < NBC; ++bc) {
+                    f32x4_t b4 = {0.f, 0.f, 0.f, 0.f};
+                    b4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(q0, rb[bc][0], b4, 0, 0, 0);
+                    b4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(q1, rb[bc][1], b4, 0, 0, 0);
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) bias_s[(16 * ci + 4 * g + r) * bstride + 16 * bc + j] = b4[r];
-                    }
-                // the chunk's Q and dO rows, as B operands of the second products
-                uint2* dq = reinterpret_cast<uint2*>(q_s + (16 * ci + j) * kVStride + 16 * g);
-                uint2* dg = reinterpret_cast<uint2*>(g_s + (16 * ci + j) * kVStride + 16 * g);
-                dq[0] = make_uint2(qa[ci][0].w.x, qa[ci][0].w.y);
-                dq[1] = make_uint2(qa[ci][0].w.z, qa[ci][0].w.w);
-                dq[2] = make_uint2(qa[ci][1].w.x, qa[ci][1].w.y);
-                dq[3] = make_uint2(qa[ci][1].w.z, qa[ci][1].w.w);
-                dg[0] = make_uint2(ga[ci][0].w.x, ga[ci][0].w.y);
-                dg[1] = make_uint2(ga[ci][0].w.z, ga[ci][0].w.w);
-                dg[2] = make_uint2(ga[ci][1].w.x, ga[ci][1].w.y);
-                dg[3] = make_uint2(ga[ci][1].w.z, ga[ci][1].w.w);
+                    for (int r = 0; r < 4; ++r) bias_s[(16 * ci + 4 * g + r) * bstride + 16 * bc + j] = b4[r];
+                }
             }
             wave_lds_sync();
             float ds[2][4], pp[2][4], bv[2][4];
+            float2 st[2][4];
             int bid[2][4];
 #pragma unroll
             for (int ci = 0; ci < 2; ++ci) {
-                bid[ci][0] = (int)(short)(mp[ci].x & 0xFFFFu);
-                bid[ci][1] = (int)(short)(mp[ci].x >> 16);
-                bid[ci][2] = (int)(short)(mp[ci].y & 0xFFFFu);
-                bid[ci][3] = (int)(short)(mp[ci].y >> 16);
+                const float4 x = *reinterpret_cast<const float4*>(stat_s + 16 * ci + 4 * g);
+                const float4 y = *reinterpret_cast<const float4*>(stat_s + 16 * ci + 4 * g + 2);
+                st[ci][0] = make_float2(x.x, x.y);
+                st[ci][1] = make_float2(x.z, x.w);
+                st[ci][2] = make_float2(y.x, y.y);
+                st[ci][3] = make_float2(y.z, y.w);
+            }
+#pragma unroll
+            for (int ci = 0; ci < 2; ++ci) {
+                bid[ci][0] = (int)(short)(mpc[ci].x & 0xFFFFu);
+                bid[ci][1] = (int)(short)(mpc[ci].x >> 16);
+                bid[ci][2] = (int)(short)(mpc[ci].y & 0xFFFFu);
+                bid[ci][3] = (int)(short)(mpc[ci].y >> 16);
 #pragma unroll
                 for (int r = 0; r < 4; ++r) bv[ci][r] = bias_s[(16 * ci + 4 * g + r) * bstride + max(bid[ci][r], 0)];
             }
@@ -2075,7 +2119,7 @@ __global__ void __launch_bounds__(kTileThreads) bwd_kv_tile_kernel(const KeyArgs
             const bf16x8_t pH = __builtin_bit_cast(bf16x8_t, xph), pL = __builtin_bit_cast(bf16x8_t, xpl);
 #pragma unroll
             for (int f = 0; f < 4; ++f) {
-                const bf16x8_t qB = lds_transposed_b(q_s, kVStride, f, g, j), gB = lds_transposed_b(g_s, kVStride, f, g, j);
+                const bf16x8_t qB = lds_transposed_b(q_s, kRowStride, f, g, j), gB = lds_transposed_b(g_s, kRowStride, f, g, j);
                 dk[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sH, qB, dk[f], 0, 0, 0);
                 dk[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sL, qB, dk[f], 0, 0, 0);
                 dv[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pH, gB, dv[f], 0, 0, 0);
@@ -2526,7 +2570,8 @@ int plan_bwd(const bpt_graph* g, const bpt_shape_t* s, BwdPlan* p) {
             p->drel_lds += (size_t)kD * (nids + 8) * sizeof(bf16_t);  // Rel^T
         }
         if (g->ktiles.num_tasks > 0 && g->ktiles.nb_pad <= 16 * kMaxBiasChunks) {
-            p->kv_lds = (size_t)kTileWaves * (32 * (g->ktiles.nb_pad + 1) * sizeof(float) + 64 * kVStride * sizeof(bf16_t));
+            p->kv_lds = (size_t)kTileWaves * (32 * (g->ktiles.nb_pad + 1) * sizeof(float) + 64 * kRowStride * sizeof(bf16_t) +
+                                              32 * sizeof(float2));
             p->kv_tiles = p->kv_lds <= lim.lds;
         }
         p->drel_grid_y = (p->drel_rows + kRgIds - 1) / kRgIds;
@@ -2633,6 +2678,17 @@ int run_bwd_q(const bpt_graph* g, const BwdPlan& p, AttnArgs& a, hipStream_t st)
     return BPT_OK;
 }
 
+template <int NBC>
+int launch_kv_tiles(const KeyArgs& t, const BwdPlan& p, const DeviceLimits& lim, hipStream_t st) {
+    if (p.kv_lds > 65536)
+        BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_kv_tile_kernel<NBC>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.kv_lds));
+    const int grid = std::max(8, lim.cus * resident_blocks(bwd_kv_tile_kernel<NBC>, kTileThreads, p.kv_lds, lim) / 8 * 8);
+    BPT_LAUNCH("bwd_kv_tile_kernel", bwd_kv_tile_kernel<NBC>, dim3(grid), dim3(kTileThreads), p.kv_lds, st, t);
+    BPT_HIP(hipGetLastError());
+    return BPT_OK;
+}
+
 // bf16 key side on dense tiles of key nodes
 int run_bwd_kv_tiles(const bpt_graph* g, const BwdPlan& p, const AttnArgs& a, const DeviceLimits& lim, hipStream_t st) {
     const KeyTiles& kt = g->ktiles;
@@ -2669,12 +2725,18 @@ int run_bwd_kv_tiles(const bpt_graph* g, const BwdPlan& p, const AttnArgs& a, co
     t.nb_pad = kt.nb_pad;
     t.W = g->rel_width;
     t.zero = g->k + 1;
-    if (p.kv_lds > 65536)
-        BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_kv_tile_kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.kv_lds));
-    const int grid = std::max(8, lim.cus * resident_blocks(bwd_kv_tile_kernel, kTileThreads, p.kv_lds, lim) / 8 * 8);
-    BPT_LAUNCH("bwd_kv_tile_kernel", bwd_kv_tile_kernel, dim3(grid), dim3(kTileThreads), p.kv_lds, st, t);
-    BPT_HIP(hipGetLastError());
+    t.num_chunks = kt.num_chunks;
+    int rc = BPT_ERR_UNSUPPORTED;
+    switch (kt.nb_pad / 16) {
+        case 1: rc = launch_kv_tiles<1>(t, p, lim, st); break;
+        case 2: rc = launch_kv_tiles<2>(t, p, lim, st); break;
+        case 3: rc = launch_kv_tiles<3>(t, p, lim, st); break;
+        case 4: rc = launch_kv_tiles<4>(t, p, lim, st); break;
+        case 5: rc = launch_kv_tiles<5>(t, p, lim, st); break;
+        case 6: rc = launch_kv_tiles<6>(t, p, lim, st); break;
+        default: break;
+    }
+    if (rc) return rc;
     if (kt.num_multi > 0) {
         BPT_LAUNCH("kv_tile_merge_kernel", kv_tile_merge_kernel, dim3(a.BH * kt.num_multi), dim3(256), 0, st, t, kt.multi_tile,
                            kt.multi_ptr, kt.num_multi);

@@ -620,6 +620,7 @@ int make_key_tiles(int32_t n, int32_t k, int32_t num_levels, int32_t ctx_levels,
             multi_ptr.push_back(parts);
         }
     }
+    out.num_chunks = chunk_ptr.back();
     out.nb_pad = (W + num_levels - 1 + 15) & ~15;
     out.first_uncovered = (int32_t)level_offset(n, ctx_levels);
     out.num_multi = (int32_t)multi_tile.size();

@@ -54,6 +54,7 @@ struct TokenTiles {
 constexpr int kKeyTaskChunks = 32;
 struct KeyTiles {
     int32_t num_tasks = 0, num_multi = 0, num_part = 0;
+    int32_t num_chunks = 0;         // chunks of all tiles together
     int32_t nb_pad = 0;             // relative-position ids a tile can meet, padded to 16
     int32_t first_uncovered = 0;    // nodes from here on have no in-edges (levels without contextual edges)
     int32_t* tile_node0 = nullptr;  // [tiles] first key node
