@@ -1435,6 +1435,184 @@ __global__ void __launch_bounds__(kTileThreads) bwd_q_tile_kernel(const TileArgs
 }
 
 
+// d_rel and the relative-position part of dQ over the token tiles' compact ids (bf16
+// tensors, at most 256 ids in use).  Per block of 32 token rows the workgroup builds
+// DS^T[id][row] (hi and lo halves) in LDS from the (w, p) pairs of the query side: every
+// edge of a token row carries a 16-bit code = compact id * 32 + row % 32 (tile metadata),
+// so an edge needs no search for its row and no lookup of its id.  Q rows are staged
+// row-major and enter the products through transposing LDS reads:
+//   d_rel[id][f] += DS^T (A, 16-byte rows) x Q (B, transposed read),
+//   dQ[row][f]   += scale * DS (A, transposed read of DS^T) x Rel (B, transposed read).
+// Wavefront w owns id chunks w and w + 8; its accumulators live across the blocks the
+// workgroup walks and are written once, as this workgroup's copy, in compact-id order.
+struct RelGradArgs {
+    const bf16_t *Q, *rel;
+    float* dQ;
+    const float2 *stat, *wp;
+    float* drel_part;
+    const int32_t *row_ptr, *cid_to_id;
+    const int16_t* ecode;
+    int64_t sb, sh, sn, e_tok;
+    int32_t BH, H, N, n, num_cids, nids;   // nids = ids padded to 32
+    float scale;
+};
+// 8 consecutive k of the operand row/column `col0 + j`: two transposing reads of 4 rows each
+__device__ __forceinline__ bf16x8_t lds_tr8(const bf16_t* base, int stride, int row0, int col0, int j) {
+    typedef __attribute__((address_space(3))) s16x4_t* lds_ptr_t;
+    const bf16_t* p = base + (row0 + (j >> 2)) * stride + col0 + 4 * (j & 3);
+    const s16x4_t x = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)p);
+    const s16x4_t y = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p + 4 * stride));
+    typedef short s16x8_t __attribute__((ext_vector_type(8)));
+    const s16x8_t xy = {x[0], x[1], x[2], x[3], y[0], y[1], y[2], y[3]};
+    return __builtin_bit_cast(bf16x8_t, xy);
+}
+
+constexpr int kRgPrefetch = 6;   // edges per thread fetched one block ahead (512 threads: 3072 edges)
+__global__ void __launch_bounds__(kThreads) rel_grad_tile_kernel(const RelGradArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int nids = a.nids;
+    bf16_t* ds_hi = reinterpret_cast<bf16_t*>(smem);                 // [nids][kRgStride]: DS^T, rows of the block along a line
+    bf16_t* ds_lo = ds_hi + nids * kRgStride;
+    bf16_t* q_s = ds_lo + nids * kRgStride;                          // [32 rows][kRowStride]
+    bf16_t* rel_s = q_s + kRgRows * kRowStride;                      // [nids][kRelStride], compact order
+    __shared__ float delta_s[kRgRows];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int g = lane >> 4, j = lane & 15;
+    for (int i = threadIdx.x; i < nids * 8; i += blockDim.x) {
+        const int cid = i >> 3, c8 = (i & 7) * 8;
+        uint4 w = make_uint4(0u, 0u, 0u, 0u);
+        if (cid < a.num_cids) w = *reinterpret_cast<const uint4*>(a.rel + (int64_t)a.cid_to_id[cid] * kD + c8);
+        *reinterpret_cast<uint4*>(rel_s + cid * kRelStride + c8) = w;
+    }
+    const int blocks_per_bh = (a.n + kRgRows - 1) / kRgRows;
+    const int total = a.BH * blocks_per_bh;
+    const int nchunks = nids >> 4;
+    const rsrc_t rCode = make_rsrc(a.ecode, (uint32_t)a.e_tok * 2u);
+
+    f32x4_t acc[2][4];
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int f = 0; f < 4; ++f) acc[c][f] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    // What a block needs from memory is requested one block ahead, so that it arrives while
+    // the current block's products run: the thread's piece of a Q row (or a delta), and its
+    // first kRgPrefetch edges (code and (w, p) pair; offsets past the block read zeros).
+    uint4 qpiece = make_uint4(0u, 0u, 0u, 0u);
+    float dl_own = 0.f;
+    int code[kRgPrefetch];
+    float2 wpv[kRgPrefetch];
+    int e_begin = 0, e_end = 0;
+    auto prefetch = [&](int blk) {
+        const int bh = blk / blocks_per_bh, row0 = (blk - bh * blocks_per_bh) * kRgRows;
+        const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
+        e_begin = a.row_ptr[row0];
+        e_end = a.row_ptr[min(row0 + kRgRows, a.n)];
+        qpiece = make_uint4(0u, 0u, 0u, 0u);
+        if (threadIdx.x < kRgRows * 8) {
+            const int r = threadIdx.x >> 3, c = (threadIdx.x & 7) * 8;
+            if (row0 + r < a.n) qpiece = *reinterpret_cast<const uint4*>(a.Q + base + (int64_t)(row0 + r) * a.sn + c);
+        } else if (threadIdx.x < kRgRows * 8 + kRgRows) {
+            const int r = threadIdx.x - kRgRows * 8;
+            dl_own = row0 + r < a.n ? a.stat[(int64_t)bh * a.N + row0 + r].y : 0.f;
+        }
+        const rsrc_t rWp = make_rsrc(a.wp + (int64_t)bh * a.e_tok, (uint32_t)a.e_tok * 8u);
+#pragma unroll
+        for (int k = 0; k < kRgPrefetch; ++k) {
+            const int e = e_begin + (int)threadIdx.x + k * kThreads;
+            const uint32_t off = e < e_end ? (uint32_t)e : 0x1FFFFFFFu;   // past the block: an offset outside the buffers
+            code[k] = (int)__builtin_amdgcn_raw_buffer_load_b16(rCode, (int)(off * 2u), 0, 0);
+            wpv[k] = buf_f2(rWp, (int)(off * 8u));
+        }
+    };
+    if ((int)blockIdx.x < total) prefetch(blockIdx.x);
+
+    for (int blk = blockIdx.x; blk < total; blk += gridDim.x) {
+        const int bh = blk / blocks_per_bh, row0 = (blk - bh * blocks_per_bh) * kRgRows;
+        const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
+        // clear DS^T (hi and lo are adjacent), stage the block's Q rows and deltas
+        for (int i = threadIdx.x * 8; i < 2 * nids * kRgStride; i += blockDim.x * 8)
+            *reinterpret_cast<uint4*>(ds_hi + i) = make_uint4(0u, 0u, 0u, 0u);
+        if (threadIdx.x < kRgRows * 8)
+            *reinterpret_cast<uint4*>(q_s + (threadIdx.x >> 3) * kRowStride + (threadIdx.x & 7) * 8) = qpiece;
+        else if (threadIdx.x < kRgRows * 8 + kRgRows)
+            delta_s[threadIdx.x - kRgRows * 8] = dl_own;
+        __syncthreads();
+        // scatter dS = w - delta * p of the block's edges (contiguous in the CSR), one thread per edge
+        auto scatter = [&](int c, float2 x) {
+            const int r = c & 31, cid = c >> 5;
+            const float ds = x.x - delta_s[r] * x.y;
+            uint32_t hi, lo;
+            split_pack(ds, 0.f, hi, lo);
+            ds_hi[cid * kRgStride + r] = (bf16_t)hi;
+            ds_lo[cid * kRgStride + r] = (bf16_t)lo;
+        };
+        const int cur_begin = e_begin, cur_end = e_end;
+#pragma unroll
+        for (int k = 0; k < kRgPrefetch; ++k)
+            if (cur_begin + (int)threadIdx.x + k * kThreads < cur_end) scatter(code[k], wpv[k]);
+        {   // blocks with more edges than were fetched ahead
+            const float2* wp_b = a.wp + (int64_t)bh * a.e_tok;
+            for (int e = cur_begin + (int)threadIdx.x + kRgPrefetch * kThreads; e < cur_end; e += kThreads)
+                scatter(a.ecode[e], wp_b[e]);
+        }
+        // the dQ values this thread will add to, and everything the next block needs
+        const int mc = wave >> 2, fc = wave & 3;
+        float dq_old[4];
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            const int row = row0 + 16 * mc + 4 * g + m;
+            dq_old[m] = row < a.n ? a.dQ[base + (int64_t)row * a.sn + 16 * fc + j] : 0.f;
+        }
+        if (blk + (int)gridDim.x < total) prefetch(blk + gridDim.x);
+        __syncthreads();
+        {   // dQ of the block: wavefront -> 16 rows x 16 features
+            f32x4_t dq = {0.f, 0.f, 0.f, 0.f};
+            for (int ks = 0; ks < nids; ks += 32) {
+                const bf16x8_t rb = lds_tr8(rel_s, kRelStride, ks + 8 * g, 16 * fc, j);
+                dq = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lds_tr8(ds_hi, kRgStride, ks + 8 * g, 16 * mc, j), rb, dq, 0, 0, 0);
+                dq = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lds_tr8(ds_lo, kRgStride, ks + 8 * g, 16 * mc, j), rb, dq, 0, 0, 0);
+            }
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                const int row = row0 + 16 * mc + 4 * g + m;
+                if (row < a.n) a.dQ[base + (int64_t)row * a.sn + 16 * fc + j] = dq_old[m] + a.scale * dq[m];
+            }
+        }
+        bf16x8_t qb[4];
+#pragma unroll
+        for (int f = 0; f < 4; ++f) qb[f] = lds_tr8(q_s, kRowStride, 8 * g, 16 * f, j);
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const int chunk = wave + kWaves * c;
+            if (chunk < nchunks) {
+                const int off = (16 * chunk + j) * kRgStride + 8 * g;
+                const bf16x8_t ah = *reinterpret_cast<const bf16x8_t*>(ds_hi + off);
+                const bf16x8_t al = *reinterpret_cast<const bf16x8_t*>(ds_lo + off);
+#pragma unroll
+                for (int f = 0; f < 4; ++f) {
+                    acc[c][f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, qb[f], acc[c][f], 0, 0, 0);
+                    acc[c][f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al, qb[f], acc[c][f], 0, 0, 0);
+                }
+            }
+        }
+        __syncthreads();
+    }
+    // this workgroup's copy: [gridDim.x][nids][kD], compact-id order
+    float* dst = a.drel_part + (int64_t)blockIdx.x * nids * kD;
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        const int chunk = wave + kWaves * c;
+        if (chunk < nchunks) {
+#pragma unroll
+            for (int f = 0; f < 4; ++f)
+#pragma unroll
+                for (int m = 0; m < 4; ++m) dst[(16 * chunk + 4 * g + m) * kD + 16 * f + j] = acc[c][f][m] * a.scale;
+        }
+    }
+}
+
 // ---- span rows on the matrix cores (bf16): blocks of 32 tokens -------------------------
 // Span node (l, m) attends to exactly the 2^l tokens it contains (Sec. 3.2.2, affiliated
 // edges), so all span rows over a block of 32 consecutive tokens share the block's K and
@@ -2209,13 +2387,17 @@ __global__ void __launch_bounds__(256) bwd_kv_merge_kernel(const AttnArgs a, con
 // cover are zero.  One workgroup per row of 64 features: 16 wavefronts each sum a
 // sixteenth of the copies (lane = feature, coalesced 256-byte reads, four
 // independent partial sums in flight), then combine in a fixed tree.
+// With `id_to_cid` the copies are in the token tiles' compact-id order and hold
+// `covered_rows` rows each: row `id` of d_rel is copy row id_to_cid[id] (or zero).
 __global__ void __launch_bounds__(1024) drel_reduce_kernel(const float* __restrict__ parts, int num_parts,
-                                                           int covered_rows, float* __restrict__ d_rel) {
+                                                           int covered_rows, const int32_t* __restrict__ id_to_cid,
+                                                           float* __restrict__ d_rel) {
     __shared__ float s[16][kD];
     const int row = blockIdx.x, lane = threadIdx.x & 63, grp = threadIdx.x >> 6;
+    const int prow = id_to_cid ? id_to_cid[row] : row;
     float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-    if (row < covered_rows) {
-        const float* src = parts + (int64_t)row * kD + lane;
+    if (prow >= 0 && prow < covered_rows) {
+        const float* src = parts + (int64_t)prow * kD + lane;
         const int64_t stride = (int64_t)covered_rows * kD;
         int p = grp;
         for (; p + 48 < num_parts; p += 64) {
@@ -2542,6 +2724,8 @@ int run_fwd(const bpt_graph* g, AttnArgs& a, hipStream_t st) {
 struct BwdPlan {
     int drel_rows = 0;        // d_rel rows token rows can touch
     bool drel_mfma = false;   // bf16 tensors: rel_grad_mfma_kernel; fp32: rel_grad_kernel
+    bool drel_tile = false;   // bf16 tensors with token tiles and at most 256 ids in use: rel_grad_tile_kernel
+    int drel_part_rows = 0;   // rows of one workgroup's copy of d_rel
     bool q_tiles = false;     // query side of token rows on dense tiles (bwd_q_tile_kernel)
     bool kv_tiles = false;    // key side on dense tiles of key nodes (bwd_kv_tile_kernel)
     size_t kv_lds = 0;
@@ -2569,12 +2753,19 @@ int plan_bwd(const bpt_graph* g, const bpt_shape_t* s, BwdPlan* p) {
             p->q_tiles = true;
             p->drel_lds += (size_t)kD * (nids + 8) * sizeof(bf16_t);  // Rel^T
         }
+        if (tlds > 0 && tlds <= lim.lds && g->tiles.ecode && g->tiles.num_cids <= kRgIds) {
+            p->q_tiles = true;
+            p->drel_tile = true;
+            const int cids = (g->tiles.num_cids + 31) & ~31;
+            p->drel_part_rows = cids;
+            p->drel_lds = ((size_t)2 * cids * kRgStride + kRgRows * kRowStride + (size_t)cids * kRelStride) * sizeof(bf16_t);
+        }
         if (g->ktiles.num_tasks > 0 && g->ktiles.nb_pad <= 16 * kMaxBiasChunks) {
             p->kv_lds = (size_t)kTileWaves * (32 * (g->ktiles.nb_pad + 1) * sizeof(float) + 64 * kRowStride * sizeof(bf16_t) +
                                               32 * sizeof(float2));
             p->kv_tiles = p->kv_lds <= lim.lds;
         }
-        p->drel_grid_y = (p->drel_rows + kRgIds - 1) / kRgIds;
+        p->drel_grid_y = p->drel_tile ? 1 : (p->drel_rows + kRgIds - 1) / kRgIds;
         blocks = (int64_t)s->B * s->H * ((g->n + kRgRows - 1) / kRgRows);
     } else {
         p->drel_ipw = p->drel_rows <= 64 ? 8 : p->drel_rows <= 128 ? 16 : 32;
@@ -2599,7 +2790,8 @@ int plan_bwd(const bpt_graph* g, const bpt_shape_t* s, BwdPlan* p) {
     off += align_up(bh * std::max<size_t>(g->tr.num_part, p->kv_tiles ? (size_t)g->ktiles.num_part * 16 : 0) * 2 * kD *
                     sizeof(float));
     p->off_drel = off;
-    off += align_up((size_t)p->drel_grid_x * p->drel_rows * kD * sizeof(float));
+    if (!p->drel_tile) p->drel_part_rows = p->drel_rows;
+    off += align_up((size_t)p->drel_grid_x * p->drel_part_rows * kD * sizeof(float));
     p->total = off;
     return BPT_OK;
 }
@@ -2655,7 +2847,35 @@ int run_bwd_q(const bpt_graph* g, const BwdPlan& p, AttnArgs& a, hipStream_t st)
                            sc->multi_ptr, sc->num_multi);
         BPT_HIP(hipGetLastError());
     }
-    if (p.drel_mfma) {
+    if (p.drel_tile) {
+        RelGradArgs t = {};
+        t.Q = static_cast<const bf16_t*>(a.Q);
+        t.rel = static_cast<const bf16_t*>(a.rel);
+        t.dQ = a.dQ;
+        t.stat = a.stat;
+        t.wp = a.wp;
+        t.drel_part = a.drel_part;
+        t.row_ptr = g->row_ptr;
+        t.cid_to_id = g->tiles.cid_to_id;
+        t.ecode = g->tiles.ecode;
+        t.sb = a.sb;
+        t.sh = a.sh;
+        t.sn = a.sn;
+        t.e_tok = a.e_tok;
+        t.BH = a.BH;
+        t.H = a.H;
+        t.N = a.N;
+        t.n = g->n;
+        t.num_cids = g->tiles.num_cids;
+        t.nids = p.drel_part_rows;
+        t.scale = a.scale;
+        if (p.drel_lds > 65536)
+            BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rel_grad_tile_kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.drel_lds));
+        BPT_LAUNCH("rel_grad_tile_kernel", rel_grad_tile_kernel, dim3(p.drel_grid_x), dim3(kThreads), p.drel_lds, st, t);
+        BPT_HIP(hipGetLastError());
+        rc = BPT_OK;
+    } else if (p.drel_mfma) {
         if (p.drel_lds > 65536)
             BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rel_grad_mfma_kernel<true>),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.drel_lds));
@@ -2673,7 +2893,7 @@ int run_bwd_q(const bpt_graph* g, const BwdPlan& p, AttnArgs& a, hipStream_t st)
     }
     if (rc) return rc;
     BPT_LAUNCH("drel_reduce_kernel", drel_reduce_kernel, dim3(a.rel_rows), dim3(1024), 0, st, a.drel_part, p.drel_grid_x,
-                       p.drel_rows, a.d_rel);
+               p.drel_part_rows, p.drel_tile ? g->tiles.id_to_cid : nullptr, a.d_rel);
     BPT_HIP(hipGetLastError());
     return BPT_OK;
 }

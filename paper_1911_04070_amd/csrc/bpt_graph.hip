@@ -437,6 +437,8 @@ void free_tiles(TokenTiles& t) {
     (void)hipFree(t.map);
     (void)hipFree(t.emap);
     (void)hipFree(t.cid_to_id);
+    (void)hipFree(t.id_to_cid);
+    (void)hipFree(t.ecode);
     t = TokenTiles();
 }
 
@@ -503,6 +505,13 @@ int make_token_tiles(int32_t n, int32_t k, int32_t num_levels, const std::vector
     out.num_cids = (int32_t)cid_to_id.size();
     out.num_chunks = chunk_ptr.back();
     int rc;
+    if ((rc = upload(cid, &out.id_to_cid))) return rc;
+    if (cid_to_id.size() <= 1024) {  // the edge codes of the d_rel kernel: 10 bits of id, 5 bits of row
+        std::vector<int16_t> ecode((size_t)ptr[n]);
+        for (int32_t u = 0; u < n; ++u)
+            for (int32_t x = ptr[u]; x < ptr[u + 1]; ++x) ecode[x] = (int16_t)(cid[rel[x]] * 32 + (u & 31));
+        if ((rc = upload(ecode, &out.ecode))) return rc;
+    }
     if ((rc = upload(chunk_ptr, &out.chunk_ptr)) || (rc = upload(cols, &out.cols)) || (rc = upload(map, &out.map)) ||
         (rc = upload(emap, &out.emap)) || (rc = upload(cid_to_id, &out.cid_to_id)))
         return rc;
