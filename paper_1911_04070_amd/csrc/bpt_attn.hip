@@ -853,11 +853,6 @@ constexpr int kRgRows = 32;     // token rows per block = K of one MFMA
 constexpr int kRgStride = 40;   // bf16 elements per LDS row (32 + padding)
 constexpr int kRgIds = 256;     // ids per workgroup
 
-// ADD_DQ: also add the relative-position part of dQ of the block's rows,
-// dQ_rel = scale * DS Rel (the tile kernel leaves it out); needs all ids in one
-// workgroup (gridDim.y == 1).  Wavefront w computes rows 16*(w/4).. and features
-// 16*(w%4).. of the 32 x 64 block: A = DS (read transposed out of DS^T), B = Rel^T.
-template <bool ADD_DQ>
 __global__ void __launch_bounds__(kThreads) rel_grad_mfma_kernel(const AttnArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int id0 = blockIdx.y * kRgIds;
@@ -865,21 +860,6 @@ __global__ void __launch_bounds__(kThreads) rel_grad_mfma_kernel(const AttnArgs 
     bf16_t* ds_hi = reinterpret_cast<bf16_t*>(smem);                // [nids][kRgStride]
     bf16_t* ds_lo = ds_hi + nids * kRgStride;
     bf16_t* q_t = ds_lo + nids * kRgStride;                         // [kD][kRgStride]
-    bf16_t* rel_t = q_t + kD * kRgStride;                           // [kD][nids + 8]   (ADD_DQ)
-    const int rt_stride = nids + 8;
-    if (ADD_DQ) {
-        for (int i = threadIdx.x; i < nids * 8; i += blockDim.x) {
-            const int id = i >> 3, c = (i & 7) * 8;
-            uint4 w = make_uint4(0u, 0u, 0u, 0u);
-            if (id < a.drel_rows) w = *reinterpret_cast<const uint4*>(static_cast<const bf16_t*>(a.rel) + (int64_t)id * kD + c);
-            const uint32_t x[4] = {w.x, w.y, w.z, w.w};
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                rel_t[(c + 2 * t) * rt_stride + id] = (bf16_t)(x[t] & 0xFFFFu);
-                rel_t[(c + 2 * t + 1) * rt_stride + id] = (bf16_t)(x[t] >> 16);
-            }
-        }
-    }
     __shared__ int row_s[kRgRows + 1];
     __shared__ float delta_s[kRgRows];
     const int lane = threadIdx.x & 63;
@@ -940,25 +920,6 @@ __global__ void __launch_bounds__(kThreads) rel_grad_mfma_kernel(const AttnArgs 
             }
         }
         __syncthreads();
-        if (ADD_DQ) {
-            const int mc = wave >> 2, fc = wave & 3;
-            f32x4_t dq = {0.f, 0.f, 0.f, 0.f};
-            for (int ks = 0; ks < nids; ks += 32) {
-                const bf16_t* col = ds_hi + (ks + 8 * g) * kRgStride + 16 * mc + j;   // DS[row][id] = DS^T[id][row]
-                u32x4 x;
-                x.x = (uint32_t)col[0] | ((uint32_t)col[kRgStride] << 16);
-                x.y = (uint32_t)col[2 * kRgStride] | ((uint32_t)col[3 * kRgStride] << 16);
-                x.z = (uint32_t)col[4 * kRgStride] | ((uint32_t)col[5 * kRgStride] << 16);
-                x.w = (uint32_t)col[6 * kRgStride] | ((uint32_t)col[7 * kRgStride] << 16);
-                const bf16x8_t rb = *reinterpret_cast<const bf16x8_t*>(rel_t + (16 * fc + j) * rt_stride + ks + 8 * g);
-                dq = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, x), rb, dq, 0, 0, 0);
-            }
-#pragma unroll
-            for (int m = 0; m < 4; ++m) {
-                const int row = row0 + 16 * mc + 4 * g + m;
-                if (row < a.n_tokens) a.dQ[base + (int64_t)row * a.sn + 16 * fc + j] += a.scale * dq[m];
-            }
-        }
         bf16x8_t qb[4];
 #pragma unroll
         for (int f = 0; f < 4; ++f)
@@ -1019,7 +980,6 @@ constexpr int kTileWaves = kTileThreads / 64;
 constexpr int kRelStride = 72;   // bf16 per LDS row of the compact table (64 + padding: 144 B)
 constexpr int kVStride = 68;     // bf16 per LDS row of a staged V row (136 B)
 constexpr int kRowStride = 72;   // bf16 per LDS row where rows are written and read 16 bytes at a time (144 B)
-constexpr int kGroup = 4;        // chunks per softmax group
 
 struct TileArgs {
     const bf16_t *Q, *K, *V, *rel;
@@ -1038,9 +998,6 @@ struct TileArgs {
     const float* lse_r;
     float* dQ;
     float2 *stat, *wp;
-    int64_t e_tok;
-    const int16_t* emap;
-    const int32_t* row_ptr;
 };
 
 __device__ __forceinline__ void wave_lds_sync() {  // order LDS traffic between the lanes of one wavefront
@@ -1048,7 +1005,6 @@ __device__ __forceinline__ void wave_lds_sync() {  // order LDS traffic between 
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
-__device__ __forceinline__ bf16x8_t as_bf16x8(const Row<bf16_t>& r) { return __builtin_bit_cast(bf16x8_t, r.w); }
 // two floats -> packed bf16 pair, round to nearest even (one v_cvt_pk_bf16_f32)
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
     typedef __bf16 bf16x2v_t __attribute__((ext_vector_type(2)));
@@ -1077,17 +1033,25 @@ __device__ __forceinline__ bf16x8_t lds_transposed_b(const bf16_t* rows, int str
     return __builtin_bit_cast(bf16x8_t, xy);
 }
 
-__global__ void __launch_bounds__(kTileThreads) fwd_tile_kernel(const TileArgs a) {
+// Position of a wavefront in its sequence of (token tile, pair of chunks); wave-uniform.
+struct TileCursor {
+    int t, pair, npairs, cp0, bh, tile;
+    bool valid;
+};
+
+__global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     bf16_t* rel_s = reinterpret_cast<bf16_t*>(smem);                                   // [cid_pad][kRelStride]
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int g = lane >> 4, j = lane & 15;
+    const int r8 = lane >> 3, piece = lane & 7;   // coalesced row fetches: row of the instruction, 16-byte piece
     float* bias_s = reinterpret_cast<float*>(smem + (size_t)a.cid_pad * kRelStride * sizeof(bf16_t)) +
                     (size_t)wave * 16 * a.bias_stride;                                  // [16 tokens][bias_stride]
-    bf16_t* v_s = reinterpret_cast<bf16_t*>(smem + (size_t)a.cid_pad * kRelStride * sizeof(bf16_t) +
+    bf16_t* k_s = reinterpret_cast<bf16_t*>(smem + (size_t)a.cid_pad * kRelStride * sizeof(bf16_t) +
                                             (size_t)kTileWaves * 16 * a.bias_stride * sizeof(float)) +
-                  (size_t)wave * 32 * kVStride;                                         // [32 columns][kVStride]
+                  (size_t)wave * 64 * kRowStride;                                       // [32 columns][kRowStride]: K rows
+    bf16_t* v_s = k_s + 32 * kRowStride;                                                // the same for V rows
     // compact relative-position table, zero rows as padding
     for (int i = threadIdx.x; i < a.cid_pad * 8; i += blockDim.x) {
         const int cid = i >> 3, c8 = (i & 7) * 8;
@@ -1101,158 +1065,201 @@ __global__ void __launch_bounds__(kTileThreads) fwd_tile_kernel(const TileArgs a
     const rsrc_t rC = make_rsrc(a.cols, (uint32_t)a.num_chunks * 64u);   // [chunks][16] int32
     const rsrc_t rM = make_rsrc(a.map, (uint32_t)a.num_chunks * 512u);   // [chunks][16][16] int16
     const int groups_per_bh = (a.num_tiles + kTileWaves - 1) / kTileWaves;
-    for (TileWalk w(a.BH * groups_per_bh); w.t < w.t_end; w.t += w.step) {
-        const int bh = w.t / groups_per_bh;
-        const int tile = (w.t - bh * groups_per_bh) * kTileWaves + wave;
-        if (tile >= a.num_tiles) continue;
-        const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
-        const rsrc_t rK = make_rsrc(a.K + base, a.slab_bytes), rV = make_rsrc(a.V + base, a.slab_bytes);
-        const int t0 = tile * 16;
-        const int cp0 = a.chunk_ptr[tile], nch = a.chunk_ptr[tile + 1] - cp0;
-        const int feat_off = 16 * g * (int)sizeof(bf16_t);  // this lane group's 16 features, in bytes
+    const TileWalk w(a.BH * groups_per_bh);
 
-        // Q^T operand: token j, features 16g..16g+15
-        const bf16_t* qrow = a.Q + base + (int64_t)(t0 + j) * a.sn + 16 * g;
-        const bf16x8_t qb0 = *reinterpret_cast<const bf16x8_t*>(qrow);
-        const bf16x8_t qb1 = *reinterpret_cast<const bf16x8_t*>(qrow + 8);
-
-        // bias^T = Rel x Q^T, kept in LDS as [token][compact id]
-        for (int c = 0; c < a.cid_pad; c += 16) {
-            const bf16_t* rrow = rel_s + (c + j) * kRelStride + 16 * g;
-            f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(rrow), qb0, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(rrow + 8), qb1, acc, 0, 0, 0);
-            *reinterpret_cast<f32x4_t*>(bias_s + j * a.bias_stride + c + 4 * g) = acc;
+    // One sequence of pairs of chunks through the wavefront's tiles, software pipelined as in
+    // bwd_q_tile_kernel: `cc` is computed, the rows of `cr` and the ids of `ci` are in flight.
+    auto enter_tile = [&](TileCursor& c) {
+        c.valid = false;
+        c.pair = 0;
+        c.npairs = 1;
+        for (; c.t < w.t_end; c.t += w.step) {
+            c.bh = c.t / groups_per_bh;
+            c.tile = (c.t - c.bh * groups_per_bh) * kTileWaves + wave;
+            if (c.tile < a.num_tiles) {
+                c.cp0 = a.chunk_ptr[c.tile];
+                c.npairs = (a.chunk_ptr[c.tile + 1] - c.cp0) >> 1;
+                c.valid = true;
+                return;
+            }
         }
+    };
+    auto advance = [&](TileCursor& c) {
+        if (c.valid && ++c.pair == c.npairs) {
+            c.t += w.step;
+            enter_tile(c);
+        }
+    };
+    int node_n[2][2];
+    uint2 mp_n[2];
+    auto load_idx = [&](const TileCursor& c) {
+#pragma unroll
+        for (int ci = 0; ci < 2; ++ci) {
+            const int at = (c.cp0 + 2 * c.pair + ci) * 16;
+            node_n[ci][0] = buf_i32(rC, (at + r8) * 4);
+            node_n[ci][1] = buf_i32(rC, (at + 8 + r8) * 4);
+            const u32x2 m2 = __builtin_amdgcn_raw_buffer_load_b64(rM, (at + j) * 32 + 8 * g, 0, 0);
+            mp_n[ci] = make_uint2(m2.x, m2.y);
+        }
+    };
+    Row<bf16_t> kr[2][2], vr[2][2];   // [chunk][half of its rows]: this lane's 16-byte piece
+    bf16x8_t qn0, qn1;                // Q^T operand of the tile whose first pair is in flight
+    auto request_rows = [&](const TileCursor& c) {
+        const int64_t base = (int64_t)(c.bh / a.H) * a.sb + (int64_t)(c.bh % a.H) * a.sh;
+        const rsrc_t rK = make_rsrc(a.K + base, a.slab_bytes), rV = make_rsrc(a.V + base, a.slab_bytes);
+#pragma unroll
+        for (int ci = 0; ci < 2; ++ci)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int off = (int)__umul24(node_n[ci][h], a.row_bytes) + piece * 16;
+                buf_row(rK, off, kr[ci][h]);
+                buf_row(rV, off, vr[ci][h]);
+            }
+        if (c.pair == 0) {   // token j, features 16g..16g+15
+            const int64_t at = base + (int64_t)(c.tile * 16 + j) * a.sn + 16 * g;
+            qn0 = *reinterpret_cast<const bf16x8_t*>(a.Q + at);
+            qn1 = *reinterpret_cast<const bf16x8_t*>(a.Q + at + 8);
+        }
+    };
+
+    TileCursor cc, cr, ci;
+    cc.t = w.t;
+    enter_tile(cc);
+    if (!cc.valid) return;
+    load_idx(cc);
+    request_rows(cc);
+    uint2 mp[2] = {mp_n[0], mp_n[1]};
+    cr = cc;
+    advance(cr);
+    if (cr.valid) load_idx(cr);
+    ci = cr;
+    advance(ci);
+
+    bf16x8_t qb0, qb1;
+    float m_run = kNegBig, l_part = 0.f;
+    f32x4_t o[4];
+
+    while (cc.valid) {
+        if (cc.pair == 0) {   // a new tile: its Q rows arrived with the rows of this pair
+            qb0 = qn0;
+            qb1 = qn1;
+            m_run = kNegBig;
+            l_part = 0.f;
+#pragma unroll
+            for (int f = 0; f < 4; ++f) o[f] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            // bias^T = Rel x Q^T, kept in LDS as [token][compact id]
+            for (int c = 0; c < a.cid_pad; c += 16) {
+                const bf16_t* rrow = rel_s + (c + j) * kRelStride + 16 * g;
+                f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(rrow), qb0, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(rrow + 8), qb1, acc, 0, 0, 0);
+                *reinterpret_cast<f32x4_t*>(bias_s + j * a.bias_stride + c + 4 * g) = acc;
+            }
+        }
+        wave_lds_sync();  // the previous pair's reads of k_s, v_s (and the previous tile's of bias_s) are done
+#pragma unroll
+        for (int ci2 = 0; ci2 < 2; ++ci2)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int row = 16 * ci2 + 8 * h + r8;
+                *reinterpret_cast<uint4*>(k_s + row * kRowStride + piece * 8) = kr[ci2][h].w;
+                *reinterpret_cast<uint4*>(v_s + row * kRowStride + piece * 8) = vr[ci2][h].w;
+            }
+        __builtin_amdgcn_sched_barrier(0);
+        // the row registers are free: request the next pair's rows, then the ids of the pair after it
+        const uint2 mpc[2] = {mp[0], mp[1]};
+        if (cr.valid) {
+            request_rows(cr);
+            mp[0] = mp_n[0];
+            mp[1] = mp_n[1];
+        }
+        if (ci.valid) load_idx(ci);
+        __builtin_amdgcn_sched_barrier(0);
         wave_lds_sync();
 
-        float m_run = kNegBig, l_part = 0.f;
-        f32x4_t o[4];
+        int cid[2][4];
+        float bv[2][4];
 #pragma unroll
-        for (int f = 0; f < 4; ++f) o[f] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-
-        for (int grp = 0; grp < nch; grp += kGroup) {
-            // Straight-line loads: the column ids and map words of the whole group, then all K
-            // rows, then all V rows.  A chunk past the end of the tile repeats the last chunk
-            // (valid addresses) with every column masked, so nothing here branches.
-            float sc[kGroup][4];
-            Row<bf16_t> ka[kGroup], kb[kGroup], va[kGroup], vb[kGroup];
-            int off[kGroup];
-            uint2 mp[kGroup];
+        for (int c = 0; c < 2; ++c) {
+            cid[c][0] = (int)(short)(mpc[c].x & 0xFFFFu);
+            cid[c][1] = (int)(short)(mpc[c].x >> 16);
+            cid[c][2] = (int)(short)(mpc[c].y & 0xFFFFu);
+            cid[c][3] = (int)(short)(mpc[c].y >> 16);
 #pragma unroll
-            for (int ci = 0; ci < kGroup; ++ci) {
-                const int at = (cp0 + min(grp + ci, nch - 1)) * 16 + j;
-                off[ci] = buf_i32(rC, at * 4);
-                const u32x2 m2 = __builtin_amdgcn_raw_buffer_load_b64(rM, at * 32 + 8 * g, 0, 0);
-                const bool live = grp + ci < nch;
-                mp[ci] = make_uint2(live ? m2.x : ~0u, live ? m2.y : ~0u);
-            }
+            for (int r = 0; r < 4; ++r) bv[c][r] = bias_s[j * a.bias_stride + max(cid[c][r], 0)];
+        }
+        f32x4_t s4[2];
 #pragma unroll
-            for (int ci = 0; ci < kGroup; ++ci) {
-                off[ci] = (int)__umul24(off[ci], a.row_bytes) + feat_off;
-                buf_row(rK, off[ci], ka[ci]);
-                buf_row(rK, off[ci] + 16, kb[ci]);
-            }
+        for (int c = 0; c < 2; ++c) {
+            const bf16_t* krow = k_s + (16 * c + j) * kRowStride + 16 * g;
+            s4[c] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            s4[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(krow), qb0, s4[c], 0, 0, 0);
+            s4[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(krow + 8), qb1, s4[c], 0, 0, 0);
+        }
 #pragma unroll
-            for (int ci = 0; ci < kGroup; ++ci) {
-                buf_row(rV, off[ci], va[ci]);
-                buf_row(rV, off[ci] + 16, vb[ci]);
-            }
-            __builtin_amdgcn_sched_barrier(0);  // all of the group's row loads are in flight before any use
-            // the relative-position terms of the group's 16 elements, read unconditionally
-            int cid[kGroup][4];
-            float bv[kGroup][4];
+        for (int c = 0; c < 2; ++c)
 #pragma unroll
-            for (int ci = 0; ci < kGroup; ++ci) {
-                cid[ci][0] = (int)(short)(mp[ci].x & 0xFFFFu);
-                cid[ci][1] = (int)(short)(mp[ci].x >> 16);
-                cid[ci][2] = (int)(short)(mp[ci].y & 0xFFFFu);
-                cid[ci][3] = (int)(short)(mp[ci].y >> 16);
+            for (int r = 0; r < 4; ++r) asm volatile("" : "+v"(bv[c][r]));  // reads stay out of branches on the mask
+        // online softmax over the pair's 32 columns
+        float sc[2][4], gm = kNegBig;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) bv[ci][r] = bias_s[j * a.bias_stride + max(cid[ci][r], 0)];
-            }
-#pragma unroll
-            for (int ci = 0; ci < kGroup; ++ci)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) asm volatile("" : "+v"(bv[ci][r]));  // keeps the reads out of branches on the mask
-            float gm = kNegBig;
-#pragma unroll
-            for (int ci = 0; ci < kGroup; ++ci) {
-                f32x4_t s4 = {0.f, 0.f, 0.f, 0.f};
-                s4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ka[ci]), qb0, s4, 0, 0, 0);
-                s4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kb[ci]), qb1, s4, 0, 0, 0);
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    sc[ci][r] = cid[ci][r] >= 0 ? (s4[r] + bv[ci][r]) * qscale : kNegBig;
-                    gm = fmaxf(gm, sc[ci][r]);
-                }
-            }
-            gm = fmaxf(gm, __shfl_xor(gm, 16));
-            gm = fmaxf(gm, __shfl_xor(gm, 32));
-            const float mn = fmaxf(m_run, gm);
-            const float corr = fast_exp2(m_run - mn);
-            m_run = mn;
-            float psum = 0.f;
-#pragma unroll
-            for (int ci = 0; ci < kGroup; ++ci)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const float p = sc[ci][r] > 0.5f * kNegBig ? fast_exp2(sc[ci][r] - mn) : 0.f;
-                    sc[ci][r] = p;
-                    psum += p;
-                }
-            l_part = l_part * corr + psum;
-            // the accumulators hold tokens 4g..4g+3: fetch their correction factors
+        for (int c = 0; c < 2; ++c)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const float cr = __shfl(corr, 4 * g + r);
-#pragma unroll
-                for (int f = 0; f < 4; ++f) o[f][r] *= cr;
+                sc[c][r] = cid[c][r] >= 0 ? (s4[c][r] + bv[c][r]) * qscale : kNegBig;
+                gm = fmaxf(gm, sc[c][r]);
             }
-            // out += P V, two chunks (32 columns) at a time
+        gm = fmaxf(gm, __shfl_xor(gm, 16));
+        gm = fmaxf(gm, __shfl_xor(gm, 32));
+        const float mn = fmaxf(m_run, gm);
+        const float corr = fast_exp2(m_run - mn);
+        m_run = mn;
+        float psum = 0.f;
 #pragma unroll
-            for (int pi = 0; pi < kGroup / 2; ++pi) {
-                if (grp + 2 * pi < nch) {
-                    const Row<bf16_t> v00 = va[2 * pi], v01 = vb[2 * pi], v10 = va[2 * pi + 1], v11 = vb[2 * pi + 1];
-                    wave_lds_sync();  // the previous pair's reads of v_s are done
-                    uint2* d0 = reinterpret_cast<uint2*>(v_s + j * kVStride + 16 * g);
-                    uint2* d1 = reinterpret_cast<uint2*>(v_s + (16 + j) * kVStride + 16 * g);
-                    d0[0] = make_uint2(v00.w.x, v00.w.y);
-                    d0[1] = make_uint2(v00.w.z, v00.w.w);
-                    d0[2] = make_uint2(v01.w.x, v01.w.y);
-                    d0[3] = make_uint2(v01.w.z, v01.w.w);
-                    d1[0] = make_uint2(v10.w.x, v10.w.y);
-                    d1[1] = make_uint2(v10.w.z, v10.w.w);
-                    d1[2] = make_uint2(v11.w.x, v11.w.y);
-                    d1[3] = make_uint2(v11.w.z, v11.w.w);
-                    wave_lds_sync();
-                    u32x4 pa;
-                    pa.x = pack_bf16(sc[2 * pi][0], sc[2 * pi][1]);
-                    pa.y = pack_bf16(sc[2 * pi][2], sc[2 * pi][3]);
-                    pa.z = pack_bf16(sc[2 * pi + 1][0], sc[2 * pi + 1][1]);
-                    pa.w = pack_bf16(sc[2 * pi + 1][2], sc[2 * pi + 1][3]);
-                    const bf16x8_t pA = __builtin_bit_cast(bf16x8_t, pa);
+        for (int c = 0; c < 2; ++c)
 #pragma unroll
-                    for (int f = 0; f < 4; ++f) {
-                        // B[k][n]: column k of the pair (same interleaving as P), feature 16f + j
-                        o[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pA, lds_transposed_b(v_s, kVStride, f, g, j), o[f], 0, 0, 0);
-                    }
-                }
+            for (int r = 0; r < 4; ++r) {
+                const float p = sc[c][r] > 0.5f * kNegBig ? fast_exp2(sc[c][r] - mn) : 0.f;
+                sc[c][r] = p;
+                psum += p;
             }
-        }
-        // row sums: token j is spread over the 4 lane groups
-        float l = l_part + __shfl_xor(l_part, 16);
-        l += __shfl_xor(l, 32);
-        if (g == 0) a.lse[(int64_t)bh * a.N + t0 + j] = (m_run + fast_log2(l)) * kLn2;
-        bf16_t* orow = a.out + base + (int64_t)t0 * a.sn + 16 * 0 + j;
+        l_part = l_part * corr + psum;
+        // the accumulators hold tokens 4g..4g+3: fetch their correction factors
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const float inv = 1.f / __shfl(l, 4 * g + r);
+            const float cr4 = __shfl(corr, 4 * g + r);
 #pragma unroll
-            for (int f = 0; f < 4; ++f)
-                orow[(int64_t)(4 * g + r) * a.sn + 16 * f] = (bf16_t)to_bf16_bits(o[f][r] * inv);
+            for (int f = 0; f < 4; ++f) o[f][r] *= cr4;
         }
-        wave_lds_sync();  // bias_s and v_s are reused by the next tile
+        u32x4 pa;
+        pa.x = pack_bf16(sc[0][0], sc[0][1]);
+        pa.y = pack_bf16(sc[0][2], sc[0][3]);
+        pa.z = pack_bf16(sc[1][0], sc[1][1]);
+        pa.w = pack_bf16(sc[1][2], sc[1][3]);
+        const bf16x8_t pA = __builtin_bit_cast(bf16x8_t, pa);
+#pragma unroll
+        for (int f = 0; f < 4; ++f)
+            o[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pA, lds_transposed_b(v_s, kRowStride, f, g, j), o[f], 0, 0, 0);
+
+        if (cc.pair == cc.npairs - 1) {   // the tile is complete
+            const int64_t base = (int64_t)(cc.bh / a.H) * a.sb + (int64_t)(cc.bh % a.H) * a.sh;
+            const int t0 = cc.tile * 16;
+            // row sums: token j is spread over the 4 lane groups
+            float l = l_part + __shfl_xor(l_part, 16);
+            l += __shfl_xor(l, 32);
+            if (g == 0) a.lse[(int64_t)cc.bh * a.N + t0 + j] = (m_run + fast_log2(l)) * kLn2;
+            bf16_t* orow = a.out + base + (int64_t)t0 * a.sn + j;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float inv = 1.f / __shfl(l, 4 * g + r);
+#pragma unroll
+                for (int f = 0; f < 4; ++f)
+                    orow[(int64_t)(4 * g + r) * a.sn + 16 * f] = (bf16_t)to_bf16_bits(o[f][r] * inv);
+            }
+        }
+        cc = cr;
+        cr = ci;
+        advance(ci);
     }
 }
 
@@ -1263,17 +1270,19 @@ __global__ void __launch_bounds__(kTileThreads) fwd_tile_kernel(const TileArgs a
 //   dQ_K = scale * (W K_U - delta * P K_U)       (the key part of dQ; lse is known, so
 // no online softmax and no second pass).  (w, p) of every edge goes to `wp` in CSR
 // order for the d_rel kernel, which also adds the relative-position part of dQ.
-__global__ void __launch_bounds__(kTileThreads) bwd_q_tile_kernel(const TileArgs a) {
+__global__ void __launch_bounds__(kTileThreads, 2) bwd_q_tile_kernel(const TileArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     bf16_t* rel_s = reinterpret_cast<bf16_t*>(smem);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int g = lane >> 4, j = lane & 15;
+    const int r8 = lane >> 3, piece = lane & 7;   // coalesced row fetches: row of the instruction, 16-byte piece
     float* bias_s = reinterpret_cast<float*>(smem + (size_t)a.cid_pad * kRelStride * sizeof(bf16_t)) +
                     (size_t)wave * 16 * a.bias_stride;
     bf16_t* k_s = reinterpret_cast<bf16_t*>(smem + (size_t)a.cid_pad * kRelStride * sizeof(bf16_t) +
                                             (size_t)kTileWaves * 16 * a.bias_stride * sizeof(float)) +
-                  (size_t)wave * 32 * kVStride;
+                  (size_t)wave * 64 * kRowStride;                      // [32 columns][kRowStride]: K rows
+    bf16_t* v_s = k_s + 32 * kRowStride;                                // the same for V rows
     for (int i = threadIdx.x; i < a.cid_pad * 8; i += blockDim.x) {
         const int cid = i >> 3, c8 = (i & 7) * 8;
         uint4 w = make_uint4(0u, 0u, 0u, 0u);
@@ -1285,152 +1294,207 @@ __global__ void __launch_bounds__(kTileThreads) bwd_q_tile_kernel(const TileArgs
     const float qscale = a.scale * kLog2e;
     const rsrc_t rC = make_rsrc(a.cols, (uint32_t)a.num_chunks * 64u);
     const rsrc_t rM = make_rsrc(a.map, (uint32_t)a.num_chunks * 512u);
-    const rsrc_t rE = make_rsrc(a.emap, (uint32_t)a.num_chunks * 512u);
     const int groups_per_bh = (a.num_tiles + kTileWaves - 1) / kTileWaves;
-    for (TileWalk w(a.BH * groups_per_bh); w.t < w.t_end; w.t += w.step) {
-        const int bh = w.t / groups_per_bh;
-        const int tile = (w.t - bh * groups_per_bh) * kTileWaves + wave;
-        if (tile >= a.num_tiles) continue;
-        const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
+    const TileWalk w(a.BH * groups_per_bh);
+
+    // The wavefront's work is one sequence of pairs of chunks running through its tiles.
+    // Three positions move along it: `cc` is computed, the rows of `cr` (one pair ahead) are
+    // in flight, the column ids and map words of `ci` (two pairs ahead) are in flight.
+    auto enter_tile = [&](TileCursor& c) {
+        c.valid = false;
+        c.pair = 0;
+        c.npairs = 1;
+        for (; c.t < w.t_end; c.t += w.step) {
+            c.bh = c.t / groups_per_bh;
+            c.tile = (c.t - c.bh * groups_per_bh) * kTileWaves + wave;
+            if (c.tile < a.num_tiles) {
+                c.cp0 = a.chunk_ptr[c.tile];
+                c.npairs = (a.chunk_ptr[c.tile + 1] - c.cp0) >> 1;
+                c.valid = true;
+                return;
+            }
+        }
+    };
+    auto advance = [&](TileCursor& c) {
+        if (c.valid && ++c.pair == c.npairs) {
+            c.t += w.step;
+            enter_tile(c);
+        }
+    };
+    int node_n[2][2];
+    uint2 mp_n[2];
+    auto load_idx = [&](const TileCursor& c) {
+#pragma unroll
+        for (int ci = 0; ci < 2; ++ci) {
+            const int at = (c.cp0 + 2 * c.pair + ci) * 16;
+            node_n[ci][0] = buf_i32(rC, (at + r8) * 4);
+            node_n[ci][1] = buf_i32(rC, (at + 8 + r8) * 4);
+            const u32x2 m2 = __builtin_amdgcn_raw_buffer_load_b64(rM, (at + j) * 32 + 8 * g, 0, 0);
+            mp_n[ci] = make_uint2(m2.x, m2.y);
+        }
+    };
+    Row<bf16_t> kr[2][2], vr[2][2];   // [chunk][half of its rows]: this lane's 16-byte piece
+    bf16x8_t qn0, qn1, gn0, gn1;      // operands of the tile whose first pair is in flight
+    float lse_n = 0.f;
+    auto request_rows = [&](const TileCursor& c) {
+        const int64_t base = (int64_t)(c.bh / a.H) * a.sb + (int64_t)(c.bh % a.H) * a.sh;
         const rsrc_t rK = make_rsrc(a.K + base, a.slab_bytes), rV = make_rsrc(a.V + base, a.slab_bytes);
-        const int t0 = tile * 16;
-        const int cp0 = a.chunk_ptr[tile], nch = a.chunk_ptr[tile + 1] - cp0;
-        const int feat_off = 16 * g * (int)sizeof(bf16_t);
-
-        const bf16_t* qrow = a.Q + base + (int64_t)(t0 + j) * a.sn + 16 * g;
-        const bf16_t* grow = a.dout + base + (int64_t)(t0 + j) * a.sn + 16 * g;
-        const bf16x8_t qb0 = *reinterpret_cast<const bf16x8_t*>(qrow);
-        const bf16x8_t qb1 = *reinterpret_cast<const bf16x8_t*>(qrow + 8);
-        const bf16x8_t gb0 = *reinterpret_cast<const bf16x8_t*>(grow);
-        const bf16x8_t gb1 = *reinterpret_cast<const bf16x8_t*>(grow + 8);
-        const float lse2 = a.lse_r[(int64_t)bh * a.N + t0 + j] * kLog2e;
-        const rsrc_t rW = make_rsrc(a.wp + (int64_t)bh * a.e_tok, (uint32_t)a.e_tok * 8u);
-        const int wp0 = a.row_ptr[t0 + j];  // first edge of this lane's token row
-
-        for (int c = 0; c < a.cid_pad; c += 16) {
-            const bf16_t* rrow = rel_s + (c + j) * kRelStride + 16 * g;
-            f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(rrow), qb0, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(rrow + 8), qb1, acc, 0, 0, 0);
-            *reinterpret_cast<f32x4_t*>(bias_s + j * a.bias_stride + c + 4 * g) = acc;
+#pragma unroll
+        for (int ci = 0; ci < 2; ++ci)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int off = (int)__umul24(node_n[ci][h], a.row_bytes) + piece * 16;
+                buf_row(rK, off, kr[ci][h]);
+                buf_row(rV, off, vr[ci][h]);
+            }
+        if (c.pair == 0) {   // the tile's own rows: Q^T and dO^T operands (token j, features 16g..16g+15)
+            const int64_t at = base + (int64_t)(c.tile * 16 + j) * a.sn + 16 * g;
+            qn0 = *reinterpret_cast<const bf16x8_t*>(a.Q + at);
+            qn1 = *reinterpret_cast<const bf16x8_t*>(a.Q + at + 8);
+            gn0 = *reinterpret_cast<const bf16x8_t*>(a.dout + at);
+            gn1 = *reinterpret_cast<const bf16x8_t*>(a.dout + at + 8);
+            lse_n = a.lse_r[(int64_t)c.bh * a.N + c.tile * 16 + j];
         }
+    };
+
+    TileCursor cc, cr, ci;
+    cc.t = w.t;
+    enter_tile(cc);
+    if (!cc.valid) return;
+    load_idx(cc);
+    request_rows(cc);
+    uint2 mp[2] = {mp_n[0], mp_n[1]};
+    cr = cc;
+    advance(cr);
+    if (cr.valid) load_idx(cr);
+    ci = cr;
+    advance(ci);
+
+    bf16x8_t qb0, qb1, gb0, gb1;
+    float lse2 = 0.f, dl_part = 0.f;
+    float2* wp_t = a.wp;   // this (batch, head)'s pairs, in tile order: [chunk][token][16 columns]
+    f32x4_t ow[4], op[4];
+
+    while (cc.valid) {
+        if (cc.pair == 0) {   // a new tile: its operands arrived with the rows of this pair
+            qb0 = qn0; qb1 = qn1; gb0 = gn0; gb1 = gn1;
+            lse2 = lse_n * kLog2e;
+            wp_t = a.wp + (int64_t)cc.bh * a.num_chunks * 256;
+            dl_part = 0.f;
+#pragma unroll
+            for (int f = 0; f < 4; ++f) ow[f] = op[f] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            // bias^T = Rel x Q^T, kept in LDS as [token][compact id]
+            for (int c = 0; c < a.cid_pad; c += 16) {
+                const bf16_t* rrow = rel_s + (c + j) * kRelStride + 16 * g;
+                f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(rrow), qb0, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(rrow + 8), qb1, acc, 0, 0, 0);
+                *reinterpret_cast<f32x4_t*>(bias_s + j * a.bias_stride + c + 4 * g) = acc;
+            }
+        }
+        wave_lds_sync();  // the previous pair's reads of k_s, v_s (and the previous tile's of bias_s) are done
+#pragma unroll
+        for (int ci2 = 0; ci2 < 2; ++ci2)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int row = 16 * ci2 + 8 * h + r8;
+                *reinterpret_cast<uint4*>(k_s + row * kRowStride + piece * 8) = kr[ci2][h].w;
+                *reinterpret_cast<uint4*>(v_s + row * kRowStride + piece * 8) = vr[ci2][h].w;
+            }
+        __builtin_amdgcn_sched_barrier(0);
+        // the row registers are free: request the next pair's rows, then the ids of the pair after it
+        const uint2 mpc[2] = {mp[0], mp[1]};
+        if (cr.valid) {
+            request_rows(cr);
+            mp[0] = mp_n[0]; mp[1] = mp_n[1];
+        }
+        if (ci.valid) load_idx(ci);
+        __builtin_amdgcn_sched_barrier(0);
         wave_lds_sync();
 
-        float dl_part = 0.f;
-        f32x4_t ow[4], op[4];
+        // scores and dP of the pair, the relative-position terms read unconditionally
+        int cid[2][4];
+        float bv[2][4];
 #pragma unroll
-        for (int f = 0; f < 4; ++f) ow[f] = op[f] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-
-        for (int grp = 0; grp < nch; grp += kGroup) {
-            // straight-line loads of the whole group (see fwd_tile_kernel): ids, then K and V rows
-            Row<bf16_t> ka[kGroup], kb[kGroup], va[kGroup], vb[kGroup];
-            int off[kGroup];
-            uint2 mp[kGroup], ep[kGroup];
+        for (int c = 0; c < 2; ++c) {
+            cid[c][0] = (int)(short)(mpc[c].x & 0xFFFFu);
+            cid[c][1] = (int)(short)(mpc[c].x >> 16);
+            cid[c][2] = (int)(short)(mpc[c].y & 0xFFFFu);
+            cid[c][3] = (int)(short)(mpc[c].y >> 16);
 #pragma unroll
-            for (int ci = 0; ci < kGroup; ++ci) {
-                const int at = (cp0 + min(grp + ci, nch - 1)) * 16 + j;
-                off[ci] = buf_i32(rC, at * 4);
-                const u32x2 m2 = __builtin_amdgcn_raw_buffer_load_b64(rM, at * 32 + 8 * g, 0, 0);
-                const u32x2 e2 = __builtin_amdgcn_raw_buffer_load_b64(rE, at * 32 + 8 * g, 0, 0);
-                const bool live = grp + ci < nch;
-                mp[ci] = make_uint2(live ? m2.x : ~0u, live ? m2.y : ~0u);
-                ep[ci] = make_uint2(e2.x, e2.y);
+            for (int r = 0; r < 4; ++r) bv[c][r] = bias_s[j * a.bias_stride + max(cid[c][r], 0)];
+        }
+        f32x4_t s4[2], d4[2];
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const bf16_t* krow = k_s + (16 * c + j) * kRowStride + 16 * g;
+            const bf16_t* vrow = v_s + (16 * c + j) * kRowStride + 16 * g;
+            s4[c] = d4[c] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            s4[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(krow), qb0, s4[c], 0, 0, 0);
+            s4[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(krow + 8), qb1, s4[c], 0, 0, 0);
+            d4[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(vrow), gb0, d4[c], 0, 0, 0);
+            d4[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(vrow + 8), gb1, d4[c], 0, 0, 0);
+        }
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) asm volatile("" : "+v"(bv[c][r]));  // reads stay out of branches on the mask
+        float pw[2][4], pp[2][4];
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float p = cid[c][r] >= 0 ? fast_exp2((s4[c][r] + bv[c][r]) * qscale - lse2) : 0.f;
+                const float wgt = p * d4[c][r];
+                dl_part += wgt;
+                pw[c][r] = wgt;
+                pp[c][r] = p;
             }
+            // (w, p) of this lane's 4 columns: 32 contiguous bytes, a chunk is 2 KB contiguous
+            float4* dst = reinterpret_cast<float4*>(wp_t + ((int64_t)(cc.cp0 + 2 * cc.pair + c) * 16 + j) * 16 + 4 * g);
+            dst[0] = make_float4(pw[c][0], pp[c][0], pw[c][1], pp[c][1]);
+            dst[1] = make_float4(pw[c][2], pp[c][2], pw[c][3], pp[c][3]);
+        }
+        // W and P as A operands, each split into bf16 hi + lo: A - delta*Bv cancels when a
+        // row's softmax is peaked, so the two products need more than 8 mantissa bits
+        uint32_t whi[4], wlo[4], phi[4], plo[4];
 #pragma unroll
-            for (int ci = 0; ci < kGroup; ++ci) {
-                off[ci] = (int)__umul24(off[ci], a.row_bytes) + feat_off;
-                buf_row(rK, off[ci], ka[ci]);
-                buf_row(rK, off[ci] + 16, kb[ci]);
-                buf_row(rV, off[ci], va[ci]);
-                buf_row(rV, off[ci] + 16, vb[ci]);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            int cid[kGroup][4];
-            float bv[kGroup][4];
+        for (int c = 0; c < 2; ++c) {
+            split_pack(pw[c][0], pw[c][1], whi[2 * c], wlo[2 * c]);
+            split_pack(pw[c][2], pw[c][3], whi[2 * c + 1], wlo[2 * c + 1]);
+            split_pack(pp[c][0], pp[c][1], phi[2 * c], plo[2 * c]);
+            split_pack(pp[c][2], pp[c][3], phi[2 * c + 1], plo[2 * c + 1]);
+        }
+        const u32x4 wh = {whi[0], whi[1], whi[2], whi[3]}, wl = {wlo[0], wlo[1], wlo[2], wlo[3]};
+        const u32x4 ph = {phi[0], phi[1], phi[2], phi[3]}, pl = {plo[0], plo[1], plo[2], plo[3]};
+        const bf16x8_t wH = __builtin_bit_cast(bf16x8_t, wh), wL = __builtin_bit_cast(bf16x8_t, wl);
+        const bf16x8_t pH = __builtin_bit_cast(bf16x8_t, ph), pL = __builtin_bit_cast(bf16x8_t, pl);
 #pragma unroll
-            for (int ci = 0; ci < kGroup; ++ci) {
-                cid[ci][0] = (int)(short)(mp[ci].x & 0xFFFFu);
-                cid[ci][1] = (int)(short)(mp[ci].x >> 16);
-                cid[ci][2] = (int)(short)(mp[ci].y & 0xFFFFu);
-                cid[ci][3] = (int)(short)(mp[ci].y >> 16);
+        for (int f = 0; f < 4; ++f) {
+            const bf16x8_t kB = lds_transposed_b(k_s, kRowStride, f, g, j);
+            ow[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wH, kB, ow[f], 0, 0, 0);
+            ow[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wL, kB, ow[f], 0, 0, 0);
+            op[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pH, kB, op[f], 0, 0, 0);
+            op[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pL, kB, op[f], 0, 0, 0);
+        }
+        if (cc.pair == cc.npairs - 1) {   // the tile is complete
+            const int64_t base = (int64_t)(cc.bh / a.H) * a.sb + (int64_t)(cc.bh % a.H) * a.sh;
+            const int t0 = cc.tile * 16;
+            float delta = dl_part + __shfl_xor(dl_part, 16);
+            delta += __shfl_xor(delta, 32);
+            if (g == 0) a.stat[(int64_t)cc.bh * a.N + t0 + j] = make_float2(lse2, delta);
+            float* qrow_out = a.dQ + base + (int64_t)t0 * a.sn + j;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) bv[ci][r] = bias_s[j * a.bias_stride + max(cid[ci][r], 0)];
-            }
+            for (int r = 0; r < 4; ++r) {
+                const float dr = __shfl(delta, 4 * g + r);
 #pragma unroll
-            for (int ci = 0; ci < kGroup; ++ci)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) asm volatile("" : "+v"(bv[ci][r]));  // reads stay out of branches on the mask
-#pragma unroll
-            for (int pi = 0; pi < kGroup / 2; ++pi) {
-                if (grp + 2 * pi >= nch) break;  // wave-uniform
-                float pw[2][4], pp[2][4];
-                wave_lds_sync();  // the previous pair's reads of k_s are done
-#pragma unroll
-                for (int c = 0; c < 2; ++c) {
-                    const int ci = 2 * pi + c;
-                    f32x4_t s4 = {0.f, 0.f, 0.f, 0.f}, d4 = {0.f, 0.f, 0.f, 0.f};
-                    s4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ka[ci]), qb0, s4, 0, 0, 0);
-                    s4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kb[ci]), qb1, s4, 0, 0, 0);
-                    d4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(va[ci]), gb0, d4, 0, 0, 0);
-                    d4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vb[ci]), gb1, d4, 0, 0, 0);
-                    const int eo[4] = {(int)(ep[ci].x & 0xFFFFu), (int)(ep[ci].x >> 16), (int)(ep[ci].y & 0xFFFFu),
-                                       (int)(ep[ci].y >> 16)};
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const bool valid = cid[ci][r] >= 0;
-                        const float p = valid ? fast_exp2((s4[r] + bv[ci][r]) * qscale - lse2) : 0.f;
-                        const float wgt = p * d4[r];
-                        dl_part += wgt;
-                        pw[c][r] = wgt;
-                        pp[c][r] = p;
-                        // a masked element's store gets an offset past the buffer and is dropped
-                        const u32x2 val = {__float_as_uint(wgt), __float_as_uint(p)};
-                        __builtin_amdgcn_raw_buffer_store_b64(val, rW, valid ? (wp0 + eo[r]) * 8 : -1, 0, 0);
-                    }
-                    // stage the chunk's K rows as the B operand of the second product
-                    uint2* d = reinterpret_cast<uint2*>(k_s + (16 * c + j) * kVStride + 16 * g);
-                    d[0] = make_uint2(ka[ci].w.x, ka[ci].w.y);
-                    d[1] = make_uint2(ka[ci].w.z, ka[ci].w.w);
-                    d[2] = make_uint2(kb[ci].w.x, kb[ci].w.y);
-                    d[3] = make_uint2(kb[ci].w.z, kb[ci].w.w);
-                }
-                wave_lds_sync();
-                // W and P as A operands, each split into bf16 hi + lo: A - delta*Bv cancels when a
-                // row's softmax is peaked, so the two products need more than 8 mantissa bits
-                uint32_t whi[4], wlo[4], phi[4], plo[4];
-#pragma unroll
-                for (int c = 0; c < 2; ++c) {
-                    split_pack(pw[c][0], pw[c][1], whi[2 * c], wlo[2 * c]);
-                    split_pack(pw[c][2], pw[c][3], whi[2 * c + 1], wlo[2 * c + 1]);
-                    split_pack(pp[c][0], pp[c][1], phi[2 * c], plo[2 * c]);
-                    split_pack(pp[c][2], pp[c][3], phi[2 * c + 1], plo[2 * c + 1]);
-                }
-                const u32x4 wh = {whi[0], whi[1], whi[2], whi[3]}, wl = {wlo[0], wlo[1], wlo[2], wlo[3]};
-                const u32x4 ph = {phi[0], phi[1], phi[2], phi[3]}, pl = {plo[0], plo[1], plo[2], plo[3]};
-                const bf16x8_t wH = __builtin_bit_cast(bf16x8_t, wh), wL = __builtin_bit_cast(bf16x8_t, wl);
-                const bf16x8_t pH = __builtin_bit_cast(bf16x8_t, ph), pL = __builtin_bit_cast(bf16x8_t, pl);
-#pragma unroll
-                for (int f = 0; f < 4; ++f) {
-                    const bf16x8_t kB = lds_transposed_b(k_s, kVStride, f, g, j);
-                    ow[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wH, kB, ow[f], 0, 0, 0);
-                    ow[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wL, kB, ow[f], 0, 0, 0);
-                    op[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pH, kB, op[f], 0, 0, 0);
-                    op[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pL, kB, op[f], 0, 0, 0);
-                }
+                for (int f = 0; f < 4; ++f)
+                    qrow_out[(int64_t)(4 * g + r) * a.sn + 16 * f] = a.scale * (ow[f][r] - dr * op[f][r]);
             }
         }
-        float delta = dl_part + __shfl_xor(dl_part, 16);
-        delta += __shfl_xor(delta, 32);
-        if (g == 0) a.stat[(int64_t)bh * a.N + t0 + j] = make_float2(lse2, delta);
-        float* qrow_out = a.dQ + base + (int64_t)t0 * a.sn + j;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const float dr = __shfl(delta, 4 * g + r);
-#pragma unroll
-            for (int f = 0; f < 4; ++f)
-                qrow_out[(int64_t)(4 * g + r) * a.sn + 16 * f] = a.scale * (ow[f][r] - dr * op[f][r]);
-        }
-        wave_lds_sync();
+        cc = cr;
+        cr = ci;
+        advance(ci);
     }
 }
 
@@ -1450,10 +1514,10 @@ struct RelGradArgs {
     float* dQ;
     const float2 *stat, *wp;
     float* drel_part;
-    const int32_t *row_ptr, *cid_to_id;
-    const int16_t* ecode;
-    int64_t sb, sh, sn, e_tok;
-    int32_t BH, H, N, n, num_cids, nids;   // nids = ids padded to 32
+    const int32_t *chunk_ptr, *cid_to_id;
+    const int16_t* map;
+    int64_t sb, sh, sn;
+    int32_t BH, H, N, n, num_tiles, num_chunks, num_cids, nids;   // nids = ids padded to 32
     float scale;
 };
 // 8 consecutive k of the operand row/column `col0 + j`: two transposing reads of 4 rows each
@@ -1467,7 +1531,7 @@ __device__ __forceinline__ bf16x8_t lds_tr8(const bf16_t* base, int stride, int 
     return __builtin_bit_cast(bf16x8_t, xy);
 }
 
-constexpr int kRgPrefetch = 6;   // edges per thread fetched one block ahead (512 threads: 3072 edges)
+constexpr int kRgPrefetch = 8;   // tile slots per thread fetched one block ahead (512 threads: 16 chunks)
 __global__ void __launch_bounds__(kThreads) rel_grad_tile_kernel(const RelGradArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int nids = a.nids;
@@ -1488,7 +1552,7 @@ __global__ void __launch_bounds__(kThreads) rel_grad_tile_kernel(const RelGradAr
     const int blocks_per_bh = (a.n + kRgRows - 1) / kRgRows;
     const int total = a.BH * blocks_per_bh;
     const int nchunks = nids >> 4;
-    const rsrc_t rCode = make_rsrc(a.ecode, (uint32_t)a.e_tok * 2u);
+    const rsrc_t rMap = make_rsrc(a.map, (uint32_t)a.num_chunks * 512u);
 
     f32x4_t acc[2][4];
 #pragma unroll
@@ -1498,17 +1562,19 @@ __global__ void __launch_bounds__(kThreads) rel_grad_tile_kernel(const RelGradAr
 
     // What a block needs from memory is requested one block ahead, so that it arrives while
     // the current block's products run: the thread's piece of a Q row (or a delta), and its
-    // first kRgPrefetch edges (code and (w, p) pair; offsets past the block read zeros).
+    // first kRgPrefetch tile slots (compact id from the tile map, (w, p) pair).  The slots of
+    // the block's two token tiles are contiguous: [chunk][token][16 columns].
     uint4 qpiece = make_uint4(0u, 0u, 0u, 0u);
     float dl_own = 0.f;
     int code[kRgPrefetch];
     float2 wpv[kRgPrefetch];
-    int e_begin = 0, e_end = 0;
+    int s_begin = 0, s_mid = 0, s_end = 0;   // first slot of the block, of its second tile, and the end
     auto prefetch = [&](int blk) {
-        const int bh = blk / blocks_per_bh, row0 = (blk - bh * blocks_per_bh) * kRgRows;
+        const int bh = blk / blocks_per_bh, b2 = 2 * (blk - bh * blocks_per_bh), row0 = 16 * b2;
         const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
-        e_begin = a.row_ptr[row0];
-        e_end = a.row_ptr[min(row0 + kRgRows, a.n)];
+        s_begin = a.chunk_ptr[b2] * 256;
+        s_mid = a.chunk_ptr[min(b2 + 1, a.num_tiles)] * 256;
+        s_end = a.chunk_ptr[min(b2 + 2, a.num_tiles)] * 256;
         qpiece = make_uint4(0u, 0u, 0u, 0u);
         if (threadIdx.x < kRgRows * 8) {
             const int r = threadIdx.x >> 3, c = (threadIdx.x & 7) * 8;
@@ -1517,12 +1583,12 @@ __global__ void __launch_bounds__(kThreads) rel_grad_tile_kernel(const RelGradAr
             const int r = threadIdx.x - kRgRows * 8;
             dl_own = row0 + r < a.n ? a.stat[(int64_t)bh * a.N + row0 + r].y : 0.f;
         }
-        const rsrc_t rWp = make_rsrc(a.wp + (int64_t)bh * a.e_tok, (uint32_t)a.e_tok * 8u);
+        const rsrc_t rWp = make_rsrc(a.wp + (int64_t)bh * a.num_chunks * 256, (uint32_t)a.num_chunks * 2048u);
 #pragma unroll
         for (int k = 0; k < kRgPrefetch; ++k) {
-            const int e = e_begin + (int)threadIdx.x + k * kThreads;
-            const uint32_t off = e < e_end ? (uint32_t)e : 0x1FFFFFFFu;   // past the block: an offset outside the buffers
-            code[k] = (int)__builtin_amdgcn_raw_buffer_load_b16(rCode, (int)(off * 2u), 0, 0);
+            const int sl = s_begin + (int)threadIdx.x + k * kThreads;
+            const uint32_t off = sl < s_end ? (uint32_t)sl : 0x1FFFFFFFu;   // past the block: an offset outside the buffers
+            code[k] = (int)(short)__builtin_amdgcn_raw_buffer_load_b16(rMap, (int)(off * 2u), 0, 0);
             wpv[k] = buf_f2(rWp, (int)(off * 8u));
         }
     };
@@ -1539,23 +1605,27 @@ __global__ void __launch_bounds__(kThreads) rel_grad_tile_kernel(const RelGradAr
         else if (threadIdx.x < kRgRows * 8 + kRgRows)
             delta_s[threadIdx.x - kRgRows * 8] = dl_own;
         __syncthreads();
-        // scatter dS = w - delta * p of the block's edges (contiguous in the CSR), one thread per edge
-        auto scatter = [&](int c, float2 x) {
-            const int r = c & 31, cid = c >> 5;
+        // scatter dS = w - delta * p of the block's tile slots, one thread per slot; a masked slot
+        // has the id -1; the row of a slot follows from its position
+        const int cur_begin = s_begin, cur_mid = s_mid, cur_end = s_end;
+        auto scatter = [&](int sl, int cid, float2 x) {
+            if (cid < 0) return;
+            const int r = ((sl >> 4) & 15) + (sl >= cur_mid ? 16 : 0);
             const float ds = x.x - delta_s[r] * x.y;
             uint32_t hi, lo;
             split_pack(ds, 0.f, hi, lo);
             ds_hi[cid * kRgStride + r] = (bf16_t)hi;
             ds_lo[cid * kRgStride + r] = (bf16_t)lo;
         };
-        const int cur_begin = e_begin, cur_end = e_end;
 #pragma unroll
-        for (int k = 0; k < kRgPrefetch; ++k)
-            if (cur_begin + (int)threadIdx.x + k * kThreads < cur_end) scatter(code[k], wpv[k]);
-        {   // blocks with more edges than were fetched ahead
-            const float2* wp_b = a.wp + (int64_t)bh * a.e_tok;
-            for (int e = cur_begin + (int)threadIdx.x + kRgPrefetch * kThreads; e < cur_end; e += kThreads)
-                scatter(a.ecode[e], wp_b[e]);
+        for (int k = 0; k < kRgPrefetch; ++k) {
+            const int sl = cur_begin + (int)threadIdx.x + k * kThreads;
+            if (sl < cur_end) scatter(sl, code[k], wpv[k]);
+        }
+        {   // blocks with more slots than were fetched ahead
+            const float2* wp_b = a.wp + (int64_t)bh * a.num_chunks * 256;
+            for (int sl = cur_begin + (int)threadIdx.x + kRgPrefetch * kThreads; sl < cur_end; sl += kThreads)
+                scatter(sl, a.map[sl], wp_b[sl]);
         }
         // the dQ values this thread will add to, and everything the next block needs
         const int mc = wave >> 2, fc = wave & 3;
@@ -2538,7 +2608,7 @@ size_t tile_lds_bytes(const bpt_graph* g, int* cid_pad, int* bias_stride) {
     *cid_pad = (g->tiles.num_cids + 15) & ~15;
     *bias_stride = *cid_pad + ((4 - *cid_pad % 32) + 32) % 32;  // = 4 mod 32: the 16 token rows hit different banks
     return (size_t)*cid_pad * kRelStride * sizeof(bf16_t) + (size_t)kTileWaves * 16 * *bias_stride * sizeof(float) +
-           (size_t)kTileWaves * 32 * kVStride * sizeof(bf16_t);
+           (size_t)kTileWaves * 64 * kRowStride * sizeof(bf16_t);
 }
 
 void fill_tile_args(TileArgs& t, const bpt_graph* g, const AttnArgs& a, int cid_pad, int bias_stride);
@@ -2569,9 +2639,6 @@ void fill_tile_args(TileArgs& t, const bpt_graph* g, const AttnArgs& a, int cid_
     t.dQ = a.dQ;
     t.stat = a.stat;
     t.wp = a.wp;
-    t.e_tok = a.e_tok;
-    t.emap = g->tiles.emap;
-    t.row_ptr = g->row_ptr;
     t.Q = static_cast<const bf16_t*>(a.Q);
     t.K = static_cast<const bf16_t*>(a.K);
     t.V = static_cast<const bf16_t*>(a.V);
@@ -2749,11 +2816,7 @@ int plan_bwd(const bpt_graph* g, const bpt_shape_t* s, BwdPlan* p) {
         // dense tiles for the query side: only when one workgroup of the d_rel kernel sees all ids
         int cid_pad = 0, bias_stride = 0;
         const size_t tlds = tile_lds_bytes(g, &cid_pad, &bias_stride);
-        if (tlds > 0 && tlds <= lim.lds && p->drel_rows <= kRgIds) {
-            p->q_tiles = true;
-            p->drel_lds += (size_t)kD * (nids + 8) * sizeof(bf16_t);  // Rel^T
-        }
-        if (tlds > 0 && tlds <= lim.lds && g->tiles.ecode && g->tiles.num_cids <= kRgIds) {
+        if (tlds > 0 && tlds <= lim.lds && g->tiles.num_cids <= kRgIds) {
             p->q_tiles = true;
             p->drel_tile = true;
             const int cids = (g->tiles.num_cids + 31) & ~31;
@@ -2782,7 +2845,8 @@ int plan_bwd(const bpt_graph* g, const bpt_shape_t* s, BwdPlan* p) {
     p->off_stat = off;
     off += align_up(bh * g->num_nodes * sizeof(float2));
     p->off_wp = off;
-    off += align_up(bh * (size_t)g->num_token_edges * sizeof(float2));
+    // (w, p) pairs: per edge of a token row in CSR order, or per slot of the token tiles
+    off += align_up(bh * (p->q_tiles ? (size_t)g->tiles.num_chunks * 256 : (size_t)g->num_token_edges) * sizeof(float2));
     p->off_qpart = off;
     off += align_up(bh * std::max<size_t>(std::max(g->fwd.num_part, g->fwd_span.num_part), span_partials(g)) *
                     kQPartStride * sizeof(float));
@@ -2855,17 +2919,18 @@ int run_bwd_q(const bpt_graph* g, const BwdPlan& p, AttnArgs& a, hipStream_t st)
         t.stat = a.stat;
         t.wp = a.wp;
         t.drel_part = a.drel_part;
-        t.row_ptr = g->row_ptr;
+        t.chunk_ptr = g->tiles.chunk_ptr;
         t.cid_to_id = g->tiles.cid_to_id;
-        t.ecode = g->tiles.ecode;
+        t.map = g->tiles.map;
         t.sb = a.sb;
         t.sh = a.sh;
         t.sn = a.sn;
-        t.e_tok = a.e_tok;
         t.BH = a.BH;
         t.H = a.H;
         t.N = a.N;
         t.n = g->n;
+        t.num_tiles = g->tiles.num_tiles;
+        t.num_chunks = g->tiles.num_chunks;
         t.num_cids = g->tiles.num_cids;
         t.nids = p.drel_part_rows;
         t.scale = a.scale;
@@ -2877,14 +2942,10 @@ int run_bwd_q(const bpt_graph* g, const BwdPlan& p, AttnArgs& a, hipStream_t st)
         rc = BPT_OK;
     } else if (p.drel_mfma) {
         if (p.drel_lds > 65536)
-            BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rel_grad_mfma_kernel<true>),
+            BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rel_grad_mfma_kernel),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.drel_lds));
-        if (p.q_tiles)
-            BPT_LAUNCH("rel_grad_mfma_kernel", rel_grad_mfma_kernel<true>, dim3(p.drel_grid_x, p.drel_grid_y), dim3(kThreads),
-                               p.drel_lds, st, a);
-        else
-            BPT_LAUNCH("rel_grad_mfma_kernel", rel_grad_mfma_kernel<false>, dim3(p.drel_grid_x, p.drel_grid_y), dim3(kThreads),
-                               p.drel_lds, st, a);
+        BPT_LAUNCH("rel_grad_mfma_kernel", rel_grad_mfma_kernel, dim3(p.drel_grid_x, p.drel_grid_y), dim3(kThreads), p.drel_lds,
+                   st, a);
         BPT_HIP(hipGetLastError());
         rc = BPT_OK;
     } else {

@@ -435,10 +435,8 @@ void free_tiles(TokenTiles& t) {
     (void)hipFree(t.chunk_ptr);
     (void)hipFree(t.cols);
     (void)hipFree(t.map);
-    (void)hipFree(t.emap);
     (void)hipFree(t.cid_to_id);
     (void)hipFree(t.id_to_cid);
-    (void)hipFree(t.ecode);
     t = TokenTiles();
 }
 
@@ -465,7 +463,7 @@ int make_token_tiles(int32_t n, int32_t k, int32_t num_levels, const std::vector
         return lev == 0 ? 0 : 2 * lev - 1 + (ord > 0 ? 1 : 0);
     };
     std::vector<int32_t> chunk_ptr(1, 0), cols, lo(nb), hi(nb), first(nb);
-    std::vector<int16_t> map, emap;
+    std::vector<int16_t> map;
     for (int32_t t = 0; t < tiles; ++t) {
         std::fill(lo.begin(), lo.end(), INT32_MAX);
         std::fill(hi.begin(), hi.end(), -1);
@@ -488,16 +486,13 @@ int make_token_tiles(int32_t n, int32_t k, int32_t num_levels, const std::vector
         for (int32_t q = 0; q < nb; ++q)
             for (int32_t v = lo[q]; hi[q] >= 0 && v <= hi[q]; ++v) cols[c0 + first[q] + (v - lo[q])] = v;
         map.resize(m0 + (size_t)nch * 256, (int16_t)-1);
-        emap.resize(m0 + (size_t)nch * 256, (int16_t)-1);
         for (int32_t r = 0; r < 16; ++r) {
             const int32_t rb = ptr[16 * t + r], re = ptr[16 * t + r + 1];
-            if (re - rb > 32767) return BPT_OK;  // edge offsets would not fit: no tile path
             for (int32_t x = rb; x < re; ++x) {
                 const int32_t q = bucket_of(rel[x]);
                 const int32_t slot = first[q] + col[x] - lo[q];
                 const size_t at = m0 + ((size_t)(slot >> 4) * 16 + r) * 16 + (slot & 15);
                 map[at] = (int16_t)cid[rel[x]];
-                emap[at] = (int16_t)(x - rb);
             }
         }
         chunk_ptr.push_back((int32_t)(cols.size() / 16));
@@ -506,14 +501,8 @@ int make_token_tiles(int32_t n, int32_t k, int32_t num_levels, const std::vector
     out.num_chunks = chunk_ptr.back();
     int rc;
     if ((rc = upload(cid, &out.id_to_cid))) return rc;
-    if (cid_to_id.size() <= 1024) {  // the edge codes of the d_rel kernel: 10 bits of id, 5 bits of row
-        std::vector<int16_t> ecode((size_t)ptr[n]);
-        for (int32_t u = 0; u < n; ++u)
-            for (int32_t x = ptr[u]; x < ptr[u + 1]; ++x) ecode[x] = (int16_t)(cid[rel[x]] * 32 + (u & 31));
-        if ((rc = upload(ecode, &out.ecode))) return rc;
-    }
     if ((rc = upload(chunk_ptr, &out.chunk_ptr)) || (rc = upload(cols, &out.cols)) || (rc = upload(map, &out.map)) ||
-        (rc = upload(emap, &out.emap)) || (rc = upload(cid_to_id, &out.cid_to_id)))
+        (rc = upload(cid_to_id, &out.cid_to_id)))
         return rc;
     out.num_tiles = tiles;
     return BPT_OK;

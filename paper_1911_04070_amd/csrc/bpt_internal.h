@@ -41,10 +41,8 @@ struct TokenTiles {
     int32_t* chunk_ptr = nullptr;  // [num_tiles+1] first chunk of a tile
     int32_t* cols = nullptr;       // [chunks][16] node id of a column
     int16_t* map = nullptr;        // [chunks][16 rows][16 columns] compact id of the edge, or -1
-    int16_t* emap = nullptr;       // same shape: position of the edge in its CSR row, or -1
     int32_t* cid_to_id = nullptr;  // [num_cids] compact id -> row of the relative-position table
     int32_t* id_to_cid = nullptr;  // [rows of the table] the inverse, -1 for ids no token row uses
-    int16_t* ecode = nullptr;      // [edges of token rows] compact id * 32 + row % 32; null if an id needs more than 10 bits
 };
 
 // Dense tiles over the key nodes, for the matrix-core key-side backward.  A tile is up
