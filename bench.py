@@ -153,22 +153,27 @@ def main():
     gather = 256.0 * bytes_scale
     alg_bytes = {
         "fwd_tile_kernel": gather * e_tok * bh, "bwd_q_tile_kernel": gather * e_tok * bh,
+        "fwd_span_tile_kernel": gather * e_span * bh, "bwd_q_span_tile_kernel": gather * e_span * bh,
         "bwd_kv_tile_kernel": gather * g.num_edges * bh, "bwd_kv_kernel": gather * g.num_edges * bh,
     }
-    tiles_on = "fwd_tile_kernel" in kernel_ms
-    alg_bytes["fwd_kernel"] = gather * (e_span if tiles_on else g.num_edges) * bh
-    alg_bytes["bwd_q_kernel"] = gather * (e_span if "bwd_q_tile_kernel" in kernel_ms else g.num_edges) * bh
+    # the gather kernels take whatever rows the tile kernels of this launch did not
+    fwd_rest = g.num_edges - (e_tok if "fwd_tile_kernel" in kernel_ms else 0) - (
+        e_span if "fwd_span_tile_kernel" in kernel_ms else 0)
+    bwd_rest = g.num_edges - (e_tok if "bwd_q_tile_kernel" in kernel_ms else 0) - (
+        e_span if "bwd_q_span_tile_kernel" in kernel_ms else 0)
+    alg_bytes["fwd_kernel"] = gather * fwd_rest * bh
+    alg_bytes["bwd_q_kernel"] = gather * bwd_rest * bh
     main = {k: v for k, v in kernel_ms.items() if k in alg_bytes}
     dominant = max(main, key=main.get)
     achieved = alg_bytes[dominant] / (kernel_ms[dominant] * 1e-3) / 1e9
     step_alg_bytes = gather * (3 if w.backward else 1) * edge_inst
     esz = 2 if w.dtype == "bf16" else 4
     tensor = bh * g.num_nodes * w.D
-    # every tensor touched once: fwd reads Q,K,V writes out,lse; bwd reads Q,K,V,dout,lse twice, writes dQ,dK,dV,
-    # the (lse, delta) pairs and the (p dP, p) pairs (written once, read once)
+    # the tensors of the boundary, each moved once per stage that needs it: the forward reads Q, K, V and
+    # writes out, lse; the backward reads Q, K, V, dout, lse and writes dQ, dK, dV (fp32) -- no workspace traffic
     compulsory = tensor * esz * 4 + bh * g.num_nodes * 4
     if w.backward:
-        compulsory += 2 * tensor * esz * 4 + 3 * tensor * 4 + 2 * bh * g.num_nodes * 8 + 2 * bh * e_tok * 8
+        compulsory += tensor * esz * 4 + bh * g.num_nodes * 4 + 3 * tensor * 4
     roofline = {
         "bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
         "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),

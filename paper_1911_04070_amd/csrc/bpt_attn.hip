@@ -1039,6 +1039,9 @@ struct TileCursor {
     bool valid;
 };
 
+// REL_LDS: the compact relative-position table is staged in LDS; otherwise (large tables) its rows
+// are read from memory when a tile forms its bias table.
+template <bool REL_LDS>
 __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     bf16_t* rel_s = reinterpret_cast<bf16_t*>(smem);                                   // [cid_pad][kRelStride]
@@ -1046,18 +1049,20 @@ __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArg
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int g = lane >> 4, j = lane & 15;
     const int r8 = lane >> 3, piece = lane & 7;   // coalesced row fetches: row of the instruction, 16-byte piece
-    float* bias_s = reinterpret_cast<float*>(smem + (size_t)a.cid_pad * kRelStride * sizeof(bf16_t)) +
+    const size_t rel_bytes = REL_LDS ? (size_t)a.cid_pad * kRelStride * sizeof(bf16_t) : 0;
+    float* bias_s = reinterpret_cast<float*>(smem + rel_bytes) +
                     (size_t)wave * 16 * a.bias_stride;                                  // [16 tokens][bias_stride]
-    bf16_t* k_s = reinterpret_cast<bf16_t*>(smem + (size_t)a.cid_pad * kRelStride * sizeof(bf16_t) +
-                                            (size_t)kTileWaves * 16 * a.bias_stride * sizeof(float)) +
+    bf16_t* k_s = reinterpret_cast<bf16_t*>(smem + rel_bytes + (size_t)kTileWaves * 16 * a.bias_stride * sizeof(float)) +
                   (size_t)wave * 64 * kRowStride;                                       // [32 columns][kRowStride]: K rows
     bf16_t* v_s = k_s + 32 * kRowStride;                                                // the same for V rows
     // compact relative-position table, zero rows as padding
-    for (int i = threadIdx.x; i < a.cid_pad * 8; i += blockDim.x) {
-        const int cid = i >> 3, c8 = (i & 7) * 8;
-        uint4 w = make_uint4(0u, 0u, 0u, 0u);
-        if (cid < a.num_cids) w = *reinterpret_cast<const uint4*>(a.rel + (int64_t)a.cid_to_id[cid] * kD + c8);
-        *reinterpret_cast<uint4*>(rel_s + cid * kRelStride + c8) = w;
+    if (REL_LDS) {
+        for (int i = threadIdx.x; i < a.cid_pad * 8; i += blockDim.x) {
+            const int cid = i >> 3, c8 = (i & 7) * 8;
+            uint4 w = make_uint4(0u, 0u, 0u, 0u);
+            if (cid < a.num_cids) w = *reinterpret_cast<const uint4*>(a.rel + (int64_t)a.cid_to_id[cid] * kD + c8);
+            *reinterpret_cast<uint4*>(rel_s + cid * kRelStride + c8) = w;
+        }
     }
     __syncthreads();
 
@@ -1149,10 +1154,19 @@ __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArg
             for (int f = 0; f < 4; ++f) o[f] = f32x4_t{0.f, 0.f, 0.f, 0.f};
             // bias^T = Rel x Q^T, kept in LDS as [token][compact id]
             for (int c = 0; c < a.cid_pad; c += 16) {
-                const bf16_t* rrow = rel_s + (c + j) * kRelStride + 16 * g;
+                bf16x8_t r0, r1;
+                if (REL_LDS) {
+                    const bf16_t* rrow = rel_s + (c + j) * kRelStride + 16 * g;
+                    r0 = *reinterpret_cast<const bf16x8_t*>(rrow);
+                    r1 = *reinterpret_cast<const bf16x8_t*>(rrow + 8);
+                } else {   // padding ids repeat the last real one; no column carries them
+                    const bf16_t* rrow = a.rel + (int64_t)a.cid_to_id[min(c + j, a.num_cids - 1)] * kD + 16 * g;
+                    r0 = *reinterpret_cast<const bf16x8_t*>(rrow);
+                    r1 = *reinterpret_cast<const bf16x8_t*>(rrow + 8);
+                }
                 f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(rrow), qb0, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(rrow + 8), qb1, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r0, qb0, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r1, qb1, acc, 0, 0, 0);
                 *reinterpret_cast<f32x4_t*>(bias_s + j * a.bias_stride + c + 4 * g) = acc;
             }
         }
@@ -1270,6 +1284,9 @@ __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArg
 //   dQ_K = scale * (W K_U - delta * P K_U)       (the key part of dQ; lse is known, so
 // no online softmax and no second pass).  (w, p) of every edge goes to `wp` in CSR
 // order for the d_rel kernel, which also adds the relative-position part of dQ.
+// REL_LDS: the compact relative-position table is staged in LDS; otherwise (large tables) its rows
+// are read from memory when a tile forms its bias table.
+template <bool REL_LDS>
 __global__ void __launch_bounds__(kTileThreads, 2) bwd_q_tile_kernel(const TileArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     bf16_t* rel_s = reinterpret_cast<bf16_t*>(smem);
@@ -1277,17 +1294,19 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_q_tile_kernel(const TileA
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int g = lane >> 4, j = lane & 15;
     const int r8 = lane >> 3, piece = lane & 7;   // coalesced row fetches: row of the instruction, 16-byte piece
-    float* bias_s = reinterpret_cast<float*>(smem + (size_t)a.cid_pad * kRelStride * sizeof(bf16_t)) +
+    const size_t rel_bytes = REL_LDS ? (size_t)a.cid_pad * kRelStride * sizeof(bf16_t) : 0;
+    float* bias_s = reinterpret_cast<float*>(smem + rel_bytes) +
                     (size_t)wave * 16 * a.bias_stride;
-    bf16_t* k_s = reinterpret_cast<bf16_t*>(smem + (size_t)a.cid_pad * kRelStride * sizeof(bf16_t) +
-                                            (size_t)kTileWaves * 16 * a.bias_stride * sizeof(float)) +
+    bf16_t* k_s = reinterpret_cast<bf16_t*>(smem + rel_bytes + (size_t)kTileWaves * 16 * a.bias_stride * sizeof(float)) +
                   (size_t)wave * 64 * kRowStride;                      // [32 columns][kRowStride]: K rows
     bf16_t* v_s = k_s + 32 * kRowStride;                                // the same for V rows
-    for (int i = threadIdx.x; i < a.cid_pad * 8; i += blockDim.x) {
-        const int cid = i >> 3, c8 = (i & 7) * 8;
-        uint4 w = make_uint4(0u, 0u, 0u, 0u);
-        if (cid < a.num_cids) w = *reinterpret_cast<const uint4*>(a.rel + (int64_t)a.cid_to_id[cid] * kD + c8);
-        *reinterpret_cast<uint4*>(rel_s + cid * kRelStride + c8) = w;
+    if (REL_LDS) {
+        for (int i = threadIdx.x; i < a.cid_pad * 8; i += blockDim.x) {
+            const int cid = i >> 3, c8 = (i & 7) * 8;
+            uint4 w = make_uint4(0u, 0u, 0u, 0u);
+            if (cid < a.num_cids) w = *reinterpret_cast<const uint4*>(a.rel + (int64_t)a.cid_to_id[cid] * kD + c8);
+            *reinterpret_cast<uint4*>(rel_s + cid * kRelStride + c8) = w;
+        }
     }
     __syncthreads();
 
@@ -1385,10 +1404,19 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_q_tile_kernel(const TileA
             for (int f = 0; f < 4; ++f) ow[f] = op[f] = f32x4_t{0.f, 0.f, 0.f, 0.f};
             // bias^T = Rel x Q^T, kept in LDS as [token][compact id]
             for (int c = 0; c < a.cid_pad; c += 16) {
-                const bf16_t* rrow = rel_s + (c + j) * kRelStride + 16 * g;
+                bf16x8_t r0, r1;
+                if (REL_LDS) {
+                    const bf16_t* rrow = rel_s + (c + j) * kRelStride + 16 * g;
+                    r0 = *reinterpret_cast<const bf16x8_t*>(rrow);
+                    r1 = *reinterpret_cast<const bf16x8_t*>(rrow + 8);
+                } else {   // padding ids repeat the last real one; no column carries them
+                    const bf16_t* rrow = a.rel + (int64_t)a.cid_to_id[min(c + j, a.num_cids - 1)] * kD + 16 * g;
+                    r0 = *reinterpret_cast<const bf16x8_t*>(rrow);
+                    r1 = *reinterpret_cast<const bf16x8_t*>(rrow + 8);
+                }
                 f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(rrow), qb0, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(rrow + 8), qb1, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r0, qb0, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r1, qb1, acc, 0, 0, 0);
                 *reinterpret_cast<f32x4_t*>(bias_s + j * a.bias_stride + c + 4 * g) = acc;
             }
         }
@@ -1532,6 +1560,9 @@ __device__ __forceinline__ bf16x8_t lds_tr8(const bf16_t* base, int stride, int 
 }
 
 constexpr int kRgPrefetch = 8;   // tile slots per thread fetched one block ahead (512 threads: 16 chunks)
+constexpr int kRgTileMaxIds = 512;
+// CPW: 16-id chunks per wavefront (2: up to 256 ids, 4: up to 512)
+template <int CPW>
 __global__ void __launch_bounds__(kThreads) rel_grad_tile_kernel(const RelGradArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int nids = a.nids;
@@ -1554,9 +1585,9 @@ __global__ void __launch_bounds__(kThreads) rel_grad_tile_kernel(const RelGradAr
     const int nchunks = nids >> 4;
     const rsrc_t rMap = make_rsrc(a.map, (uint32_t)a.num_chunks * 512u);
 
-    f32x4_t acc[2][4];
+    f32x4_t acc[CPW][4];
 #pragma unroll
-    for (int c = 0; c < 2; ++c)
+    for (int c = 0; c < CPW; ++c)
 #pragma unroll
         for (int f = 0; f < 4; ++f) acc[c][f] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
@@ -1654,7 +1685,7 @@ __global__ void __launch_bounds__(kThreads) rel_grad_tile_kernel(const RelGradAr
 #pragma unroll
         for (int f = 0; f < 4; ++f) qb[f] = lds_tr8(q_s, kRowStride, 8 * g, 16 * f, j);
 #pragma unroll
-        for (int c = 0; c < 2; ++c) {
+        for (int c = 0; c < CPW; ++c) {
             const int chunk = wave + kWaves * c;
             if (chunk < nchunks) {
                 const int off = (16 * chunk + j) * kRgStride + 8 * g;
@@ -1672,7 +1703,7 @@ __global__ void __launch_bounds__(kThreads) rel_grad_tile_kernel(const RelGradAr
     // this workgroup's copy: [gridDim.x][nids][kD], compact-id order
     float* dst = a.drel_part + (int64_t)blockIdx.x * nids * kD;
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {
+    for (int c = 0; c < CPW; ++c) {
         const int chunk = wave + kWaves * c;
         if (chunk < nchunks) {
 #pragma unroll
@@ -2603,15 +2634,27 @@ void use_schedule(AttnArgs& a, const Schedule& sc) {
 }
 
 // LDS of fwd_tile_kernel for this graph, or 0 if the tile path does not apply
-size_t tile_lds_bytes(const bpt_graph* g, int* cid_pad, int* bias_stride) {
-    if (g->tiles.num_tiles == 0) return 0;
-    *cid_pad = (g->tiles.num_cids + 15) & ~15;
-    *bias_stride = *cid_pad + ((4 - *cid_pad % 32) + 32) % 32;  // = 4 mod 32: the 16 token rows hit different banks
-    return (size_t)*cid_pad * kRelStride * sizeof(bf16_t) + (size_t)kTileWaves * 16 * *bias_stride * sizeof(float) +
-           (size_t)kTileWaves * 64 * kRowStride * sizeof(bf16_t);
+struct TilePlan {
+    bool ok = false;       // the token tile kernels apply
+    bool rel_lds = false;  // with the compact relative-position table staged in LDS
+    int cid_pad = 0, bias_stride = 0;
+    size_t lds = 0;
+};
+TilePlan plan_tiles(const bpt_graph* g, const DeviceLimits& lim) {
+    TilePlan t;
+    if (g->tiles.num_tiles == 0) return t;
+    t.cid_pad = (g->tiles.num_cids + 15) & ~15;
+    t.bias_stride = t.cid_pad + ((4 - t.cid_pad % 32) + 32) % 32;  // = 4 mod 32: the 16 token rows hit different banks
+    const size_t rel = (size_t)t.cid_pad * kRelStride * sizeof(bf16_t);
+    const size_t rest = (size_t)kTileWaves * 16 * t.bias_stride * sizeof(float) +
+                        (size_t)kTileWaves * 64 * kRowStride * sizeof(bf16_t);
+    t.rel_lds = rel + rest <= lim.lds;
+    t.lds = t.rel_lds ? rel + rest : rest;
+    t.ok = t.lds <= lim.lds;
+    return t;
 }
 
-void fill_tile_args(TileArgs& t, const bpt_graph* g, const AttnArgs& a, int cid_pad, int bias_stride);
+void fill_tile_args(TileArgs& t, const bpt_graph* g, const AttnArgs& a, const TilePlan& tp);
 
 template <typename K>
 int launch_tiles(const char* name, K kernel, const TileArgs& t, const DeviceLimits& lim, size_t lds, hipStream_t st) {
@@ -2626,14 +2669,14 @@ int launch_tiles(const char* name, K kernel, const TileArgs& t, const DeviceLimi
 
 // bf16 backward, query side of the token rows on dense tiles
 int run_bwd_q_tiles(const bpt_graph* g, const AttnArgs& a, const DeviceLimits& lim, hipStream_t st) {
-    int cid_pad = 0, bias_stride = 0;
-    const size_t lds = tile_lds_bytes(g, &cid_pad, &bias_stride);
+    const TilePlan tp = plan_tiles(g, lim);
     TileArgs t = {};
-    fill_tile_args(t, g, a, cid_pad, bias_stride);
-    return launch_tiles("bwd_q_tile_kernel", bwd_q_tile_kernel, t, lim, lds, st);
+    fill_tile_args(t, g, a, tp);
+    return tp.rel_lds ? launch_tiles("bwd_q_tile_kernel", bwd_q_tile_kernel<true>, t, lim, tp.lds, st)
+                      : launch_tiles("bwd_q_tile_kernel", bwd_q_tile_kernel<false>, t, lim, tp.lds, st);
 }
 
-void fill_tile_args(TileArgs& t, const bpt_graph* g, const AttnArgs& a, int cid_pad, int bias_stride) {
+void fill_tile_args(TileArgs& t, const bpt_graph* g, const AttnArgs& a, const TilePlan& tp) {
     t.dout = static_cast<const bf16_t*>(a.dout);
     t.lse_r = a.lse_r;
     t.dQ = a.dQ;
@@ -2659,8 +2702,8 @@ void fill_tile_args(TileArgs& t, const bpt_graph* g, const AttnArgs& a, int cid_
     t.num_tiles = g->tiles.num_tiles;
     t.num_chunks = g->tiles.num_chunks;
     t.num_cids = g->tiles.num_cids;
-    t.cid_pad = cid_pad;
-    t.bias_stride = bias_stride;
+    t.cid_pad = tp.cid_pad;
+    t.bias_stride = tp.bias_stride;
     t.row_bytes = a.row_bytes;
     t.slab_bytes = a.slab_bytes;
 }
@@ -2742,11 +2785,11 @@ int run_span_tiles(const bpt_graph* g, const AttnArgs& a, bool forward, hipStrea
 }
 
 // bf16 forward: token rows as dense tiles on the matrix cores, span rows with the gather kernel
-int run_fwd_tiles(const bpt_graph* g, AttnArgs& a, const DeviceLimits& lim, size_t lds, int cid_pad, int bias_stride,
-                  hipStream_t st) {
+int run_fwd_tiles(const bpt_graph* g, AttnArgs& a, const DeviceLimits& lim, const TilePlan& tp, hipStream_t st) {
     TileArgs t = {};
-    fill_tile_args(t, g, a, cid_pad, bias_stride);
-    return launch_tiles("fwd_tile_kernel", fwd_tile_kernel, t, lim, lds, st);
+    fill_tile_args(t, g, a, tp);
+    return tp.rel_lds ? launch_tiles("fwd_tile_kernel", fwd_tile_kernel<true>, t, lim, tp.lds, st)
+                      : launch_tiles("fwd_tile_kernel", fwd_tile_kernel<false>, t, lim, tp.lds, st);
 }
 
 template <typename T>
@@ -2755,10 +2798,9 @@ int run_fwd(const bpt_graph* g, AttnArgs& a, hipStream_t st) {
     int rc = device_limits(g, &lim);
     if (rc) return rc;
     if (sizeof(T) == 2) {
-        int cid_pad = 0, bias_stride = 0;
-        const size_t tlds = tile_lds_bytes(g, &cid_pad, &bias_stride);
-        if (tlds > 0 && tlds <= lim.lds) {
-            if ((rc = run_fwd_tiles(g, a, lim, tlds, cid_pad, bias_stride, st))) return rc;
+        const TilePlan tp = plan_tiles(g, lim);
+        if (tp.ok) {
+            if ((rc = run_fwd_tiles(g, a, lim, tp, st))) return rc;
             if (span_tiles_ok(g)) return run_span_tiles(g, a, true, st);
             use_schedule(a, g->fwd_span);  // the gather kernel below only sees span rows
         }
@@ -2813,15 +2855,14 @@ int plan_bwd(const bpt_graph* g, const bpt_shape_t* s, BwdPlan* p) {
         p->drel_mfma = true;
         const int nids = std::min(kRgIds, (p->drel_rows + 31) & ~31);
         p->drel_lds = ((size_t)2 * nids + kD) * kRgStride * sizeof(bf16_t);
-        // dense tiles for the query side: only when one workgroup of the d_rel kernel sees all ids
-        int cid_pad = 0, bias_stride = 0;
-        const size_t tlds = tile_lds_bytes(g, &cid_pad, &bias_stride);
-        if (tlds > 0 && tlds <= lim.lds && g->tiles.num_cids <= kRgIds) {
+        // dense tiles for the query side: when one workgroup of the d_rel kernel can hold all ids in use
+        const int cids = (g->tiles.num_cids + 31) & ~31;
+        const size_t rg_lds = ((size_t)2 * cids * kRgStride + kRgRows * kRowStride + (size_t)cids * kRelStride) * sizeof(bf16_t);
+        if (plan_tiles(g, lim).ok && cids <= kRgTileMaxIds && rg_lds + 256 <= lim.lds) {
             p->q_tiles = true;
             p->drel_tile = true;
-            const int cids = (g->tiles.num_cids + 31) & ~31;
             p->drel_part_rows = cids;
-            p->drel_lds = ((size_t)2 * cids * kRgStride + kRgRows * kRowStride + (size_t)cids * kRelStride) * sizeof(bf16_t);
+            p->drel_lds = rg_lds;
         }
         if (g->ktiles.num_tasks > 0 && g->ktiles.nb_pad <= 16 * kMaxBiasChunks) {
             p->kv_lds = (size_t)kTileWaves * (32 * (g->ktiles.nb_pad + 1) * sizeof(float) + 64 * kRowStride * sizeof(bf16_t) +
@@ -2934,10 +2975,17 @@ int run_bwd_q(const bpt_graph* g, const BwdPlan& p, AttnArgs& a, hipStream_t st)
         t.num_cids = g->tiles.num_cids;
         t.nids = p.drel_part_rows;
         t.scale = a.scale;
-        if (p.drel_lds > 65536)
-            BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rel_grad_tile_kernel),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.drel_lds));
-        BPT_LAUNCH("rel_grad_tile_kernel", rel_grad_tile_kernel, dim3(p.drel_grid_x), dim3(kThreads), p.drel_lds, st, t);
+        if (p.drel_part_rows <= 256) {
+            if (p.drel_lds > 65536)
+                BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rel_grad_tile_kernel<2>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.drel_lds));
+            BPT_LAUNCH("rel_grad_tile_kernel", rel_grad_tile_kernel<2>, dim3(p.drel_grid_x), dim3(kThreads), p.drel_lds, st, t);
+        } else {
+            if (p.drel_lds > 65536)
+                BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rel_grad_tile_kernel<4>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.drel_lds));
+            BPT_LAUNCH("rel_grad_tile_kernel", rel_grad_tile_kernel<4>, dim3(p.drel_grid_x), dim3(kThreads), p.drel_lds, st, t);
+        }
         BPT_HIP(hipGetLastError());
         rc = BPT_OK;
     } else if (p.drel_mfma) {
