@@ -27,12 +27,12 @@ HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
 # workload; the runs and their commands are in profiles/.  None where not measured.
 MEASURED_TRAFFIC = {
     "lm": {  # profiles/lm_n8192_k8_causal_bf16_kernels.md
-        "bwd_kv_tile_kernel": int((336867.9 * 2.0 + 278785.7) * 1024),
-        "rel_grad_mfma_kernel": int((126758.7 * 2.0 + 89856.0) * 1024),
-        "bwd_q_tile_kernel": int((170731.3 * 2.0 + 240730.4) * 1024),
-        "bwd_q_kernel": int((175566.1 * 2.0 + 68948.9) * 1024),
-        "fwd_tile_kernel": int((115765.1 * 2.0 + 33823.8) * 1024),
-        "fwd_kernel": int((164047.3 * 2.0 + 34632.6) * 1024),
+        "bwd_kv_tile_kernel": int((305324.3 * 2.0 + 278804.1) * 1024),
+        "bwd_q_tile_kernel": int((144328.6 * 2.0 + 309302.1) * 1024),
+        "rel_grad_tile_kernel": int((173235.0 * 2.0 + 90112.5) * 1024),
+        "fwd_tile_kernel": int((116797.8 * 2.0 + 33859.6) * 1024),
+        "bwd_q_span_tile_kernel": int((67573.0 * 2.0 + 99728.0) * 1024),
+        "fwd_span_tile_kernel": int((49572.7 * 2.0 + 49974.2) * 1024),
     },
 }
 
