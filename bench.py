@@ -35,6 +35,8 @@ MEASURED_TRAFFIC = {
         "fwd_span_tile_kernel": int((49572.7 * 2.0 + 49974.2) * 1024),
     },
 }
+# HBM bytes of one whole step (all kernels, same counters and scaling)
+MEASURED_STEP_TRAFFIC = {"lm": 2749650841}
 
 
 def parse():
@@ -183,6 +185,9 @@ def main():
         "kernel_ms": {k: round(v, 4) for k, v in sorted(kernel_ms.items(), key=lambda kv: -kv[1])},
         "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()},
         "step_algorithmic_GBs": round(step_alg_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+        "step_measured_hbm_bytes": MEASURED_STEP_TRAFFIC.get(w.name),
+        "step_measured_hbm_frac_of_peak": (round(MEASURED_STEP_TRAFFIC[w.name] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+                                           if w.name in MEASURED_STEP_TRAFFIC else None),
         "step_compulsory_bytes": int(compulsory),
         "step_compulsory_frac_of_hbm_peak": round(compulsory / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "note": "achieved counts one gathered row pair per edge-instance (the algorithmic bytes of the method); the "
