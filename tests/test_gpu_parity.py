@@ -129,6 +129,12 @@ SMALL = [
     ("f32", 64, 100, False, 1, 2), ("f32", 256, 3, True, 2, 3), ("f32", 2048, 5, False, 1, 2),
     ("bf16", 2, 1, True, 1, 1), ("bf16", 32, 2, False, 3, 2), ("bf16", 128, 200, True, 1, 2),
     ("bf16", 1024, 7, False, 2, 2), ("bf16", 4096, 3, True, 1, 3),
+    # sizes around the switches of the tile kernels: no tiles (n < 16), token tiles without span
+    # blocks (n = 16), span blocks without / with one / with several ancestor levels (n = 32, 64, 512),
+    # one token tile per wavefront group left over (n = 16 * 5 is not a power of two: n = 256 with 5 (b, h))
+    ("bf16", 8, 2, False, 2, 1), ("bf16", 16, 1, False, 1, 3), ("bf16", 16, 30, True, 2, 1),
+    ("bf16", 32, 1, True, 1, 1), ("bf16", 64, 2, False, 1, 5), ("bf16", 64, 1, True, 5, 1),
+    ("bf16", 256, 4, True, 1, 5), ("bf16", 512, 1, False, 1, 1), ("bf16", 2048, 16, False, 1, 1),
 ]
 
 
