@@ -1,0 +1,220 @@
+// Device-side helpers shared by the attention kernels: kernel arguments, lane and row helpers,
+// buffer loads, bf16 packing, the XCD-aware walk over work items.
+#pragma once
+
+#include "bpt_internal.h"
+
+namespace bpt {
+namespace {
+
+typedef uint16_t bf16_t;
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kNegBig = -1.0e30f;
+constexpr int kThreads = 512;            // 8 wavefronts per workgroup
+constexpr int kWaves = kThreads / 64;
+constexpr int kQPartStride = 132;        // query-side partial: A[64], Bv[64], delta, padding
+
+struct AttnArgs {
+    // tensors
+    const void *Q, *K, *V, *rel, *dout;
+    void* out;
+    float* lse_w;
+    const float* lse_r;
+    float *dQ, *dK, *dV, *d_rel;
+    float2* stat;            // per (batch*head, node): (lse * log2(e), delta), written by the query side
+    float2* wp;              // per (batch*head, edge of a token row): (p_e dP_e, p_e), written by the query side
+    int64_t e_tok;           // edges of token rows (they come first in the CSR)
+    float *part, *drel_part;
+    int64_t sb, sh, sn;
+    int32_t row_bytes;       // sn * sizeof(T): distance between the rows of two nodes
+    uint32_t slab_bytes;     // extent of one (batch, head) slab of Q/K/V/dout
+    uint32_t idx_bytes;      // extent of ia / ib
+    int32_t BH, H, N, n_tokens;
+    float scale;
+    // adjacency: ptr[rows+1]; ia = other endpoint (col / t_src); ib = relative-position id
+    const int32_t *ptr, *ia, *ib;
+    // schedule
+    const int32_t *seg_row, *seg_begin, *seg_part, *tile_ptr;
+    int32_t num_tiles, num_part;
+    int32_t rel_rows_lds;   // rows of the r table staged in LDS (0: read it from global memory)
+    int32_t drel_rows;      // rows of d_rel that token rows can touch (levels with contextual edges)
+    int32_t drel_block;     // token rows per block of rel_grad_kernel
+    int32_t rel_rows;       // rows of the whole table
+};
+
+// ---- lane helpers ---------------------------------------------------------------
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float x) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, true));
+}
+// sum over the 8 lanes that share an edge; every one of them gets the result
+__device__ __forceinline__ float sum8(float x) {
+    x += dpp_move<0xB1>(x);   // quad_perm [1,0,3,2]
+    x += dpp_move<0x4E>(x);   // quad_perm [2,3,0,1]
+    x += dpp_move<0x141>(x);  // row_half_mirror: the other quad of the 8-lane group
+    return x;
+}
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+
+// all 8 groups (lanes with the same feature chunk) get the sum / max
+__device__ __forceinline__ float slots_sum(float x) {
+    x += __shfl_xor(x, 8);
+    x += __shfl_xor(x, 16);
+    x += __shfl_xor(x, 32);
+    return x;
+}
+__device__ __forceinline__ float slots_max(float x) {
+    x = fmaxf(x, __shfl_xor(x, 8));
+    x = fmaxf(x, __shfl_xor(x, 16));
+    x = fmaxf(x, __shfl_xor(x, 32));
+    return x;
+}
+// Sum x[0..7] over the 8 groups with 7 exchanges instead of 24: at every step a lane
+// keeps one half of its values and hands the other half to its partner.  Returns
+// the total of element slot_elem(lane) of the lane's feature chunk.
+__device__ __forceinline__ int slot_elem(int lane) {
+    return ((lane >> 5) & 1) * 4 + ((lane >> 4) & 1) * 2 + ((lane >> 3) & 1);
+}
+__device__ __forceinline__ float reduce_slots8(const float (&x)[8], int lane) {
+    const bool h32 = lane & 32, h16 = lane & 16, h8 = lane & 8;
+    float y[4], z[2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) y[i] = (h32 ? x[i + 4] : x[i]) + __shfl_xor(h32 ? x[i] : x[i + 4], 32);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) z[i] = (h16 ? y[i + 2] : y[i]) + __shfl_xor(h16 ? y[i] : y[i + 2], 16);
+    return (h8 ? z[1] : z[0]) + __shfl_xor(h8 ? z[0] : z[1], 8);
+}
+
+// ---- 8 consecutive features of one row, as loaded -----------------------------------
+template <typename T>
+struct Row;
+template <>
+struct Row<bf16_t> {
+    uint4 w;
+};
+template <>
+struct Row<float> {
+    float4 a, b;
+};
+__device__ __forceinline__ Row<bf16_t> load_row(const bf16_t* p) {
+    Row<bf16_t> r;
+    r.w = *reinterpret_cast<const uint4*>(p);
+    return r;
+}
+__device__ __forceinline__ Row<float> load_row(const float* p) {
+    Row<float> r;
+    r.a = *reinterpret_cast<const float4*>(p);
+    r.b = *reinterpret_cast<const float4*>(p + 4);
+    return r;
+}
+__device__ __forceinline__ void unpack(const Row<bf16_t>& r, float (&x)[8]) {
+    x[0] = __uint_as_float(r.w.x << 16); x[1] = __uint_as_float(r.w.x & 0xFFFF0000u);
+    x[2] = __uint_as_float(r.w.y << 16); x[3] = __uint_as_float(r.w.y & 0xFFFF0000u);
+    x[4] = __uint_as_float(r.w.z << 16); x[5] = __uint_as_float(r.w.z & 0xFFFF0000u);
+    x[6] = __uint_as_float(r.w.w << 16); x[7] = __uint_as_float(r.w.w & 0xFFFF0000u);
+}
+__device__ __forceinline__ void unpack(const Row<float>& r, float (&x)[8]) {
+    x[0] = r.a.x; x[1] = r.a.y; x[2] = r.a.z; x[3] = r.a.w;
+    x[4] = r.b.x; x[5] = r.b.y; x[6] = r.b.z; x[7] = r.b.w;
+}
+template <typename T>
+__device__ __forceinline__ void load8(const T* p, float (&x)[8]) {
+    unpack(load_row(p), x);
+}
+// c + dot product of two 8-feature chunks, fp32 accumulation.  bf16 rows stay packed:
+// v_dot2c_f32_bf16 multiplies two pairs per instruction, so neither row is unpacked.
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+__device__ __forceinline__ float dot2_bf16(uint32_t x, uint32_t y, float c) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, x), __builtin_bit_cast(bf16x2_t, y), c, false);
+}
+__device__ __forceinline__ float dot8(const Row<bf16_t>& x, const Row<bf16_t>& y, float c) {
+    c = dot2_bf16(x.w.x, y.w.x, c);
+    c = dot2_bf16(x.w.y, y.w.y, c);
+    c = dot2_bf16(x.w.z, y.w.z, c);
+    return dot2_bf16(x.w.w, y.w.w, c);
+}
+__device__ __forceinline__ float dot8(const Row<float>& x, const Row<float>& y, float c) {
+    c += x.a.x * y.a.x; c += x.a.y * y.a.y; c += x.a.z * y.a.z; c += x.a.w * y.a.w;
+    c += x.b.x * y.b.x; c += x.b.y * y.b.y; c += x.b.z * y.b.z; c += x.b.w * y.b.w;
+    return c;
+}
+// Gathers go through buffer loads: a 32-bit byte offset per lane against a
+// wave-uniform descriptor (cheap addressing, out-of-range offsets read 0), and,
+// being intrinsics rather than plain loads, they stay where the software pipeline
+// puts them instead of being sunk to their first use.
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+__device__ __forceinline__ rsrc_t make_rsrc(const void* p, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ int buf_i32(rsrc_t r, int byte_off) {
+    return (int)__builtin_amdgcn_raw_buffer_load_b32(r, byte_off, 0, 0);
+}
+__device__ __forceinline__ float2 buf_f2(rsrc_t r, int byte_off) {
+    const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(r, byte_off, 0, 0);
+    return make_float2(__uint_as_float(v.x), __uint_as_float(v.y));
+}
+__device__ __forceinline__ void buf_row(rsrc_t r, int byte_off, Row<bf16_t>& out) {
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, 0);
+    out.w = make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void buf_row(rsrc_t r, int byte_off, Row<float>& out) {
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, 0);
+    const u32x4 w = __builtin_amdgcn_raw_buffer_load_b128(r, byte_off + 16, 0, 0);
+    out.a = make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
+    out.b = make_float4(__uint_as_float(w.x), __uint_as_float(w.y), __uint_as_float(w.z), __uint_as_float(w.w));
+}
+// the lane's 8 features of the row of `node`
+template <typename T>
+__device__ __forceinline__ Row<T> gather_row(rsrc_t r, int node, int row_bytes, int lane_off) {
+    Row<T> out;
+    buf_row(r, (int)__umul24(node, row_bytes) + lane_off, out);
+    return out;
+}
+
+__device__ __forceinline__ uint32_t to_bf16_bits(float f) {  // round to nearest even (v_cvt_pk_bf16_f32)
+    return (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)f);
+}
+__device__ __forceinline__ void store8(float* p, const float (&x)[8]) {
+    *reinterpret_cast<float4*>(p) = make_float4(x[0], x[1], x[2], x[3]);
+    *reinterpret_cast<float4*>(p + 4) = make_float4(x[4], x[5], x[6], x[7]);
+}
+__device__ __forceinline__ void store8(bf16_t* p, const float (&x)[8]) {
+    uint4 w;
+    w.x = to_bf16_bits(x[0]) | (to_bf16_bits(x[1]) << 16);
+    w.y = to_bf16_bits(x[2]) | (to_bf16_bits(x[3]) << 16);
+    w.z = to_bf16_bits(x[4]) | (to_bf16_bits(x[5]) << 16);
+    w.w = to_bf16_bits(x[6]) | (to_bf16_bits(x[7]) << 16);
+    *reinterpret_cast<uint4*>(p) = w;
+}
+__device__ __forceinline__ void store1(float* p, float x) { *p = x; }
+__device__ __forceinline__ void store1(bf16_t* p, float x) { *p = (bf16_t)to_bf16_bits(x); }
+
+// Copy `count` table elements (a multiple of 8) into LDS, 16 bytes per thread per step.
+template <typename T>
+__device__ __forceinline__ void stage_table(T* dst, const T* src, int count) {
+    constexpr int per = 16 / sizeof(T);
+    for (int i = threadIdx.x * per; i < count; i += blockDim.x * per)
+        *reinterpret_cast<uint4*>(dst + i) = *reinterpret_cast<const uint4*>(src + i);
+}
+
+// Tiles of this workgroup: the (batch*head, tile) space is split into 8 contiguous
+// shares, one per XCD (workgroup w runs on XCD w mod 8); inside a share the
+// workgroups of that XCD interleave, so they sweep it together.
+struct TileWalk {
+    int t, t_end, step;
+    __device__ TileWalk(int total) {
+        const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3, wgs = gridDim.x >> 3;
+        const int per = (total + 7) >> 3;
+        t = xcd * per + j;
+        t_end = min(total, (xcd + 1) * per);
+        step = wgs;
+    }
+};
+
+}  // namespace
+}  // namespace bpt

@@ -1,0 +1,342 @@
+// Matrix-core key side of the backward over dense tiles of key nodes (bf16), its merges, and
+// the fixed-order reduction of the d_rel copies.
+#pragma once
+
+#include "attn_token_tiles.h"
+
+namespace bpt {
+namespace {
+
+// ---- backward, key side, over dense tiles of key nodes (bf16) --------------------------
+// A wavefront owns up to 16 consecutive key nodes of one level and walks (a slice of)
+// the nodes that attend to them, 32 at a time.  With the queries on the M side,
+//   S[query][key]  = Q_chunk (A, rows from memory) x K_tile^T (B, rows from memory),
+//   dP[query][key] = dO_chunk x V_tile^T,   bias[query][id] = Q_chunk x Rel_sel^T,
+// the result C[m][n] has key n = lane%16 and queries 4*(lane/16)..+3 in the registers,
+// which is the A-operand layout of the second products (contraction over queries):
+//   dK[key][f] += dS^T x Q_chunk,   dV[key][f] += P^T x dO_chunk
+// with Q and dO rows read transposed out of LDS.  lse and the exact delta of every
+// query come from the query side (`stat`), so dS is formed in fp32 before it is
+// rounded to bf16 for the product.  No atomics: a tile whose query list is cut into
+// several tasks is summed by kv_tile_merge_kernel in task order.
+constexpr int kMaxBiasChunks = 6;
+struct KeyArgs {
+    const bf16_t *Q, *K, *V, *rel, *dout;
+    const float2* stat;
+    float *dK, *dV, *part;
+    int64_t sb, sh, sn;
+    int32_t BH, H, N, num_levels;
+    float scale;
+    int32_t row_bytes;
+    uint32_t slab_bytes;
+    const int32_t *tile_node0, *tile_info, *cols, *task_tile, *task_c0, *task_nch, *task_part;
+    const int16_t* map;
+    int32_t num_tasks, num_part, num_chunks, nb_pad, W, zero;
+};
+
+template <int NBC>
+__global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int g = lane >> 4, j = lane & 15;
+    const int r8 = lane >> 3, piece = lane & 7;   // coalesced row fetches: row of the instruction, 16-byte piece
+    const int bstride = a.nb_pad + 1;
+    float* bias_s = reinterpret_cast<float*>(smem) + (size_t)wave * 32 * bstride;               // [32 queries][ids]
+    bf16_t* q_s = reinterpret_cast<bf16_t*>(smem + (size_t)kTileWaves * 32 * bstride * sizeof(float)) +
+                  (size_t)wave * 64 * kRowStride;                                                // [32 queries][kRowStride]
+    bf16_t* g_s = q_s + 32 * kRowStride;
+    float2* stat_s = reinterpret_cast<float2*>(smem + (size_t)kTileWaves * (32 * bstride * sizeof(float) +
+                                                                            64 * kRowStride * sizeof(bf16_t))) +
+                     (size_t)wave * 32;                                                          // [32 queries] (lse, delta)
+    const float qscale = a.scale * kLog2e;
+    const int groups = (a.num_tasks + kTileWaves - 1) / kTileWaves;
+    const rsrc_t rC = make_rsrc(a.cols, (uint32_t)a.num_chunks * 64u);    // [chunks][16] int32
+    const rsrc_t rM = make_rsrc(a.map, (uint32_t)a.num_chunks * 512u);    // [chunks][16][16] int16
+
+    for (TileWalk w(a.BH * groups); w.t < w.t_end; w.t += w.step) {
+        const int bh = w.t / groups;
+        const int task = (w.t - bh * groups) * kTileWaves + wave;
+        if (task >= a.num_tasks) continue;
+        const int kt = a.task_tile[task], c0 = a.task_c0[task], nch = a.task_nch[task], part = a.task_part[task];
+        const int node0 = a.tile_node0[kt], info = a.tile_info[kt];
+        const int level = info & 255, nkeys = info >> 8;
+        const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
+        const rsrc_t rQ = make_rsrc(a.Q + base, a.slab_bytes), rG = make_rsrc(a.dout + base, a.slab_bytes);
+        const rsrc_t rS = make_rsrc(a.stat + (int64_t)bh * a.N, (uint32_t)a.N * 8u);
+
+        // Software pipeline over pairs of chunks.  `Idx` = what has to be known before a pair's
+        // rows can be requested (its column ids and map words); the rows of pair i+1 are
+        // requested in the middle of pair i, as soon as the registers of pair i's rows are free,
+        // and the ids of pair i+2 right after, so the gathers overlap the second products.
+        int node[2][2];   // [chunk][half]: query node whose row this lane helps to fetch
+        uint2 mpn[2];
+        auto load_idx = [&](int c2) {   // a pair past the end repeats the last one (valid addresses, results unused)
+            const int cc = c0 + min(c2, nch - 2);
+#pragma unroll
+            for (int ci = 0; ci < 2; ++ci) {
+                const int at = (cc + ci) * 16;
+                node[ci][0] = buf_i32(rC, (at + r8) * 4);
+                node[ci][1] = buf_i32(rC, (at + 8 + r8) * 4);
+                const u32x2 m2 = __builtin_amdgcn_raw_buffer_load_b64(rM, (at + j) * 32 + 8 * g, 0, 0);
+                mpn[ci] = make_uint2(m2.x, m2.y);
+            }
+        };
+        // Row fetches are coalesced: 8 consecutive lanes take the 8 16-byte pieces of one row, an
+        // instruction fetches 8 whole rows (two per 16-row chunk).  The rows go through LDS to get
+        // into the operand layouts of the matrix instructions.
+        Row<bf16_t> qa[2][2], ga[2][2];
+        float2 stn[2][2];   // (lse, delta) of the row, kept by the lane that fetches its first piece
+        auto load_rows = [&]() {
+#pragma unroll
+            for (int ci = 0; ci < 2; ++ci)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int off = (int)__umul24(node[ci][h], a.row_bytes) + piece * 16;
+                    buf_row(rQ, off, qa[ci][h]);
+                    buf_row(rG, off, ga[ci][h]);
+                    stn[ci][h] = buf_f2(rS, node[ci][h] * 8);
+                }
+        };
+        load_idx(0);
+
+        // B operands: the tile's keys (lane j <-> key j) and the rows of the table this level can meet
+        const int64_t krow = base + (int64_t)(node0 + min(j, nkeys - 1)) * a.sn + 16 * g;
+        const bf16x8_t kb0 = *reinterpret_cast<const bf16x8_t*>(a.K + krow);
+        const bf16x8_t kb1 = *reinterpret_cast<const bf16x8_t*>(a.K + krow + 8);
+        const bf16x8_t vb0 = *reinterpret_cast<const bf16x8_t*>(a.V + krow);
+        const bf16x8_t vb1 = *reinterpret_cast<const bf16x8_t*>(a.V + krow + 8);
+        bf16x8_t rb[NBC][2];
+#pragma unroll
+        for (int bc = 0; bc < NBC; ++bc) {
+            const int bid = 16 * bc + j;
+            int row = 0;
+            if (bid < a.W)
+                row = level * a.W + bid;                        // (level, order)
+            else if (bid - a.W + 1 < a.num_levels)
+                row = (bid - a.W + 1) * a.W + a.zero;            // r_anc of the ancestor's level
+            const bf16_t* rr = a.rel + (int64_t)row * kD + 16 * g;
+            rb[bc][0] = *reinterpret_cast<const bf16x8_t*>(rr);
+            rb[bc][1] = *reinterpret_cast<const bf16x8_t*>(rr + 8);
+        }
+        load_rows();     // pair 0 (waits for its ids)
+        uint2 mp[2] = {mpn[0], mpn[1]};
+        load_idx(2);     // ids of pair 1
+
+        f32x4_t dk[4], dv[4];
+#pragma unroll
+        for (int f = 0; f < 4; ++f) dk[f] = dv[f] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+        for (int c2 = 0; c2 < nch; c2 += 2) {
+            wave_lds_sync();  // the previous pair's LDS reads are done
+#pragma unroll
+            for (int ci = 0; ci < 2; ++ci)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int row = 16 * ci + 8 * h + r8;
+                    *reinterpret_cast<uint4*>(q_s + row * kRowStride + piece * 8) = qa[ci][h].w;
+                    *reinterpret_cast<uint4*>(g_s + row * kRowStride + piece * 8) = ga[ci][h].w;
+                    if (piece == 0) stat_s[row] = stn[ci][h];
+                }
+            __builtin_amdgcn_sched_barrier(0);
+            // the row registers are free: request the next pair's rows, then the ids of the pair after it
+            const uint2 mpc[2] = {mp[0], mp[1]};
+            load_rows();
+            mp[0] = mpn[0];
+            mp[1] = mpn[1];
+            load_idx(c2 + 4);
+            __builtin_amdgcn_sched_barrier(0);
+            wave_lds_sync();
+            f32x4_t s4[2], d4[2];
+#pragma unroll
+            for (int ci = 0; ci < 2; ++ci) {
+                const bf16_t* qr = q_s + (16 * ci + j) * kRowStride + 16 * g;
+                const bf16_t* gr = g_s + (16 * ci + j) * kRowStride + 16 * g;
+                const bf16x8_t q0 = *reinterpret_cast<const bf16x8_t*>(qr), q1 = *reinterpret_cast<const bf16x8_t*>(qr + 8);
+                const bf16x8_t g0 = *reinterpret_cast<const bf16x8_t*>(gr), g1 = *reinterpret_cast<const bf16x8_t*>(gr + 8);
+                s4[ci] = d4[ci] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                s4[ci] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(q0, kb0, s4[ci], 0, 0, 0);
+                s4[ci] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(q1, kb1, s4[ci], 0, 0, 0);
+                d4[ci] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(g0, vb0, d4[ci], 0, 0, 0);
+                d4[ci] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(g1, vb1, d4[ci], 0, 0, 0);
+#pragma unroll
+                for (int bc = 0; bc < NBC; ++bc) {
+                    f32x4_t b4 = {0.f, 0.f, 0.f, 0.f};
+                    b4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(q0, rb[bc][0], b4, 0, 0, 0);
+                    b4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(q1, rb[bc][1], b4, 0, 0, 0);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) bias_s[(16 * ci + 4 * g + r) * bstride + 16 * bc + j] = b4[r];
+                }
+            }
+            wave_lds_sync();
+            float ds[2][4], pp[2][4], bv[2][4];
+            float2 st[2][4];
+            int bid[2][4];
+#pragma unroll
+            for (int ci = 0; ci < 2; ++ci) {
+                const float4 x = *reinterpret_cast<const float4*>(stat_s + 16 * ci + 4 * g);
+                const float4 y = *reinterpret_cast<const float4*>(stat_s + 16 * ci + 4 * g + 2);
+                st[ci][0] = make_float2(x.x, x.y);
+                st[ci][1] = make_float2(x.z, x.w);
+                st[ci][2] = make_float2(y.x, y.y);
+                st[ci][3] = make_float2(y.z, y.w);
+            }
+#pragma unroll
+            for (int ci = 0; ci < 2; ++ci) {
+                bid[ci][0] = (int)(short)(mpc[ci].x & 0xFFFFu);
+                bid[ci][1] = (int)(short)(mpc[ci].x >> 16);
+                bid[ci][2] = (int)(short)(mpc[ci].y & 0xFFFFu);
+                bid[ci][3] = (int)(short)(mpc[ci].y >> 16);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) bv[ci][r] = bias_s[(16 * ci + 4 * g + r) * bstride + max(bid[ci][r], 0)];
+            }
+#pragma unroll
+            for (int ci = 0; ci < 2; ++ci)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) asm volatile("" : "+v"(bv[ci][r]));  // reads stay out of branches on the mask
+#pragma unroll
+            for (int ci = 0; ci < 2; ++ci)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float p = bid[ci][r] >= 0 ? fast_exp2((s4[ci][r] + bv[ci][r]) * qscale - st[ci][r].x) : 0.f;
+                    pp[ci][r] = p;
+                    ds[ci][r] = p * (d4[ci][r] - st[ci][r].y);
+                }
+            // dS and P as A operands, each as bf16 hi + lo: the sums run over up to thousands of
+            // queries and the tolerance is absolute, so 8 mantissa bits are not enough
+            uint32_t shi[4], slo[4], phi[4], plo[4];
+#pragma unroll
+            for (int ci = 0; ci < 2; ++ci) {
+                split_pack(ds[ci][0], ds[ci][1], shi[2 * ci], slo[2 * ci]);
+                split_pack(ds[ci][2], ds[ci][3], shi[2 * ci + 1], slo[2 * ci + 1]);
+                split_pack(pp[ci][0], pp[ci][1], phi[2 * ci], plo[2 * ci]);
+                split_pack(pp[ci][2], pp[ci][3], phi[2 * ci + 1], plo[2 * ci + 1]);
+            }
+            const u32x4 xsh = {shi[0], shi[1], shi[2], shi[3]}, xsl = {slo[0], slo[1], slo[2], slo[3]};
+            const u32x4 xph = {phi[0], phi[1], phi[2], phi[3]}, xpl = {plo[0], plo[1], plo[2], plo[3]};
+            const bf16x8_t sH = __builtin_bit_cast(bf16x8_t, xsh), sL = __builtin_bit_cast(bf16x8_t, xsl);
+            const bf16x8_t pH = __builtin_bit_cast(bf16x8_t, xph), pL = __builtin_bit_cast(bf16x8_t, xpl);
+#pragma unroll
+            for (int f = 0; f < 4; ++f) {
+                const bf16x8_t qB = lds_transposed_b(q_s, kRowStride, f, g, j), gB = lds_transposed_b(g_s, kRowStride, f, g, j);
+                dk[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sH, qB, dk[f], 0, 0, 0);
+                dk[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sL, qB, dk[f], 0, 0, 0);
+                dv[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pH, gB, dv[f], 0, 0, 0);
+                dv[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pL, gB, dv[f], 0, 0, 0);
+            }
+        }
+        // C[m = key][n = feature]: lane holds keys 4g..4g+3, feature 16f + j
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int key = 4 * g + r;
+            if (key < nkeys) {
+                if (part < 0) {
+                    const int64_t at = base + (int64_t)(node0 + key) * a.sn + j;
+#pragma unroll
+                    for (int f = 0; f < 4; ++f) {
+                        a.dK[at + 16 * f] = a.scale * dk[f][r];
+                        a.dV[at + 16 * f] = dv[f][r];
+                    }
+                } else {
+                    float* dst = a.part + (((int64_t)bh * a.num_part + part) * 16 + key) * (2 * kD) + j;
+#pragma unroll
+                    for (int f = 0; f < 4; ++f) {
+                        dst[16 * f] = a.scale * dk[f][r];
+                        dst[kD + 16 * f] = dv[f][r];
+                    }
+                }
+            }
+        }
+        wave_lds_sync();
+    }
+}
+
+// tiles whose query list was cut into several tasks: sum the partial (dK, dV) of the
+// tile's keys in task order.  One workgroup per (batch*head, tile); thread -> (key, feature pair).
+__global__ void __launch_bounds__(256) kv_tile_merge_kernel(const KeyArgs a, const int32_t* __restrict__ multi_tile,
+                                                            const int32_t* __restrict__ multi_ptr, int num_multi) {
+    const int bh = blockIdx.x / num_multi, mt = blockIdx.x - bh * num_multi;
+    const int kt = multi_tile[mt];
+    const int node0 = a.tile_node0[kt], nkeys = a.tile_info[kt] >> 8;
+    const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
+    for (int i = threadIdx.x; i < nkeys * kD; i += blockDim.x) {
+        const int key = i >> 6, f = i & 63;
+        float sk = 0.f, sv = 0.f;
+        for (int p = multi_ptr[mt]; p < multi_ptr[mt + 1]; ++p) {
+            const float* src = a.part + (((int64_t)bh * a.num_part + p) * 16 + key) * (2 * kD) + f;
+            sk += src[0];
+            sv += src[kD];
+        }
+        const int64_t at = base + (int64_t)(node0 + key) * a.sn + f;
+        a.dK[at] = sk;
+        a.dV[at] = sv;
+    }
+}
+
+// nodes no one attends to (levels above the coarsest contextual level): zero gradients
+__global__ void kv_zero_rows_kernel(const KeyArgs a, int first_row) {
+    const int rows = a.N - first_row;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (int64_t)a.BH * rows * kD) return;
+    const int f = (int)(i & 63);
+    const int64_t rr = i >> 6;
+    const int bh = (int)(rr / rows), row = first_row + (int)(rr - (int64_t)bh * rows);
+    const int64_t at = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh + (int64_t)row * a.sn + f;
+    a.dK[at] = 0.f;
+    a.dV[at] = 0.f;
+}
+
+// key nodes cut into several segments: sum the (dK, dV) partials in segment order
+__global__ void __launch_bounds__(256) bwd_kv_merge_kernel(const AttnArgs a, const int32_t* __restrict__ multi_row,
+                                                           const int32_t* __restrict__ multi_ptr, int num_multi) {
+    const int lane = threadIdx.x & 63;
+    const int item = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (item >= a.BH * num_multi) return;
+    const int bh = item / num_multi, j = item - bh * num_multi;
+    float sk = 0.f, sv = 0.f;
+    for (int p = multi_ptr[j]; p < multi_ptr[j + 1]; ++p) {
+        const float* src = a.part + ((int64_t)bh * a.num_part + p) * (2 * kD);
+        sk += src[lane];
+        sv += src[kD + lane];
+    }
+    const int64_t at = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh + (int64_t)multi_row[j] * a.sn + lane;
+    a.dK[at] = sk;
+    a.dV[at] = sv;
+}
+
+// d_rel = sum of the workgroups' copies, in a fixed order; rows the copies do not
+// cover are zero.  One workgroup per row of 64 features: 16 wavefronts each sum a
+// sixteenth of the copies (lane = feature, coalesced 256-byte reads, four
+// independent partial sums in flight), then combine in a fixed tree.
+// With `id_to_cid` the copies are in the token tiles' compact-id order and hold
+// `covered_rows` rows each: row `id` of d_rel is copy row id_to_cid[id] (or zero).
+__global__ void __launch_bounds__(1024) drel_reduce_kernel(const float* __restrict__ parts, int num_parts,
+                                                           int covered_rows, const int32_t* __restrict__ id_to_cid,
+                                                           float* __restrict__ d_rel) {
+    __shared__ float s[16][kD];
+    const int row = blockIdx.x, lane = threadIdx.x & 63, grp = threadIdx.x >> 6;
+    const int prow = id_to_cid ? id_to_cid[row] : row;
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    if (prow >= 0 && prow < covered_rows) {
+        const float* src = parts + (int64_t)prow * kD + lane;
+        const int64_t stride = (int64_t)covered_rows * kD;
+        int p = grp;
+        for (; p + 48 < num_parts; p += 64) {
+            a0 += src[p * stride];
+            a1 += src[(p + 16) * stride];
+            a2 += src[(p + 32) * stride];
+            a3 += src[(p + 48) * stride];
+        }
+        for (; p < num_parts; p += 16) a0 += src[p * stride];
+    }
+    s[grp][lane] = (a0 + a1) + (a2 + a3);
+    __syncthreads();
+    for (int w = 8; w > 0; w >>= 1) {
+        if (grp < w) s[grp][lane] += s[grp + w][lane];
+        __syncthreads();
+    }
+    if (grp == 0) d_rel[row * kD + lane] = s[0][lane];
+}
+
+}  // namespace
+}  // namespace bpt

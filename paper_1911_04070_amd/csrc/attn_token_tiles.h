@@ -1,0 +1,768 @@
+// Matrix-core kernels over dense tiles of 16 token rows (bf16): forward, query side of the
+// backward, and d_rel / the relative-position part of dQ from the tiles' (w, p) pairs.
+#pragma once
+
+#include "attn_device.h"
+#include "attn_gather.h"
+
+namespace bpt {
+namespace {
+
+// ---- forward over dense tiles of token rows, on the matrix cores (bf16) ---------------
+// A wavefront computes 16 consecutive token rows against the union U of their key
+// nodes (tile metadata of the graph).  Consecutive tokens share almost all coarse
+// neighbours, so the 16 x |U| score tile is more than half full and the products
+// Q K^T and P V are real dense contractions:
+//   S^T chunk [16 columns x 16 tokens] = K_chunk (A, rows straight from memory) x Q^T (B),
+//   bias^T [ids x 16 tokens]            = Rel (A, from LDS)                    x Q^T (B),
+//   out [16 tokens x 64]               += P (A) x V_chunk (B, transposed through LDS).
+// With v_mfma_f32_16x16x32_bf16 the result C[m][n] lives in lane n + 16*(m/4),
+// register m%4 -- for S^T that is token n = lane%16 and columns 4*(lane/16)..+3, which
+// is exactly the A-operand layout P needs for the second product (A[m][k] in lane
+// m + 16*(k/8)) once the columns of two chunks are interleaved as k = 8g+i:
+// i<4 -> chunk 2c, column 4g+i; i>=4 -> chunk 2c+1, column 4g+i-4.  The feature
+// dimension of the first product is permuted the same way in both operands (lane
+// group g owns features 16g..16g+15), which leaves the dot products unchanged.
+// Softmax runs online over groups of 8 chunks; masked and padding columns carry
+// the id -1 in the tile map.
+constexpr int kTileThreads = 256;
+constexpr int kTileWaves = kTileThreads / 64;
+constexpr int kRelStride = 72;   // bf16 per LDS row of the compact table (64 + padding: 144 B)
+constexpr int kVStride = 68;     // bf16 per LDS row of a staged V row (136 B)
+constexpr int kRowStride = 72;   // bf16 per LDS row where rows are written and read 16 bytes at a time (144 B)
+
+struct TileArgs {
+    const bf16_t *Q, *K, *V, *rel;
+    bf16_t* out;
+    float* lse;
+    int64_t sb, sh, sn;
+    int32_t BH, H, N;
+    float scale;
+    const int32_t *chunk_ptr, *cols, *cid_to_id;
+    const int16_t* map;
+    int32_t num_tiles, num_chunks, num_cids, cid_pad, bias_stride;
+    int32_t row_bytes;
+    uint32_t slab_bytes;
+    // backward, query side
+    const bf16_t* dout;
+    const float* lse_r;
+    float* dQ;
+    float2 *stat, *wp;
+};
+
+__device__ __forceinline__ void wave_lds_sync() {  // order LDS traffic between the lanes of one wavefront
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+// two floats -> packed bf16 pair, round to nearest even (one v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    typedef __bf16 bf16x2v_t __attribute__((ext_vector_type(2)));
+    const bf16x2v_t v = {(__bf16)lo, (__bf16)hi};
+    return __builtin_bit_cast(uint32_t, v);
+}
+// two floats -> packed bf16 pair of their leading parts and packed bf16 pair of the remainders
+__device__ __forceinline__ void split_pack(float x, float y, uint32_t& hi, uint32_t& lo) {
+    hi = pack_bf16(x, y);
+    lo = pack_bf16(x - __uint_as_float(hi << 16), y - __uint_as_float(hi & 0xFFFF0000u));
+}
+// B operand of v_mfma_f32_16x16x32_bf16 out of rows staged in LDS: `rows` points at 32
+// staged rows (two chunks of 16) of `stride` bf16 each.  Lane (g, j) receives feature
+// 16f + j of rows 4g..4g+3 of the first chunk and of the second chunk -- the k order in
+// which the score tiles' C layout serves as the A operand.  ds_read_b64_tr_b16 reads,
+// per 16-lane group, a 4-row x 16-column block (lane 4r + c addresses columns 4c..4c+3
+// of row r) and hands lane i column i of the 4 rows.
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ bf16x8_t lds_transposed_b(const bf16_t* rows, int stride, int f, int g, int j) {
+    typedef __attribute__((address_space(3))) s16x4_t* lds_ptr_t;
+    const bf16_t* p = rows + (4 * g + (j >> 2)) * stride + 16 * f + 4 * (j & 3);
+    const s16x4_t x = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)p);
+    const s16x4_t y = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p + 16 * stride));
+    typedef short s16x8_t __attribute__((ext_vector_type(8)));
+    const s16x8_t xy = {x[0], x[1], x[2], x[3], y[0], y[1], y[2], y[3]};
+    return __builtin_bit_cast(bf16x8_t, xy);
+}
+
+// Position of a wavefront in its sequence of (token tile, pair of chunks); wave-uniform.
+struct TileCursor {
+    int t, pair, npairs, cp0, bh, tile;
+    bool valid;
+};
+
+// REL_LDS: the compact relative-position table is staged in LDS; otherwise (large tables) its rows
+// are read from memory when a tile forms its bias table.
+template <bool REL_LDS>
+__global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    bf16_t* rel_s = reinterpret_cast<bf16_t*>(smem);                                   // [cid_pad][kRelStride]
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int g = lane >> 4, j = lane & 15;
+    const int r8 = lane >> 3, piece = lane & 7;   // coalesced row fetches: row of the instruction, 16-byte piece
+    const size_t rel_bytes = REL_LDS ? (size_t)a.cid_pad * kRelStride * sizeof(bf16_t) : 0;
+    float* bias_s = reinterpret_cast<float*>(smem + rel_bytes) +
+                    (size_t)wave * 16 * a.bias_stride;                                  // [16 tokens][bias_stride]
+    bf16_t* k_s = reinterpret_cast<bf16_t*>(smem + rel_bytes + (size_t)kTileWaves * 16 * a.bias_stride * sizeof(float)) +
+                  (size_t)wave * 64 * kRowStride;                                       // [32 columns][kRowStride]: K rows
+    bf16_t* v_s = k_s + 32 * kRowStride;                                                // the same for V rows
+    // compact relative-position table, zero rows as padding
+    if (REL_LDS) {
+        for (int i = threadIdx.x; i < a.cid_pad * 8; i += blockDim.x) {
+            const int cid = i >> 3, c8 = (i & 7) * 8;
+            uint4 w = make_uint4(0u, 0u, 0u, 0u);
+            if (cid < a.num_cids) w = *reinterpret_cast<const uint4*>(a.rel + (int64_t)a.cid_to_id[cid] * kD + c8);
+            *reinterpret_cast<uint4*>(rel_s + cid * kRelStride + c8) = w;
+        }
+    }
+    __syncthreads();
+
+    const float qscale = a.scale * kLog2e;
+    const rsrc_t rC = make_rsrc(a.cols, (uint32_t)a.num_chunks * 64u);   // [chunks][16] int32
+    const rsrc_t rM = make_rsrc(a.map, (uint32_t)a.num_chunks * 512u);   // [chunks][16][16] int16
+    const int groups_per_bh = (a.num_tiles + kTileWaves - 1) / kTileWaves;
+    const TileWalk w(a.BH * groups_per_bh);
+
+    // One sequence of pairs of chunks through the wavefront's tiles, software pipelined as in
+    // bwd_q_tile_kernel: `cc` is computed, the rows of `cr` and the ids of `ci` are in flight.
+    auto enter_tile = [&](TileCursor& c) {
+        c.valid = false;
+        c.pair = 0;
+        c.npairs = 1;
+        for (; c.t < w.t_end; c.t += w.step) {
+            c.bh = c.t / groups_per_bh;
+            c.tile = (c.t - c.bh * groups_per_bh) * kTileWaves + wave;
+            if (c.tile < a.num_tiles) {
+                c.cp0 = a.chunk_ptr[c.tile];
+                c.npairs = (a.chunk_ptr[c.tile + 1] - c.cp0) >> 1;
+                c.valid = true;
+                return;
+            }
+        }
+    };
+    auto advance = [&](TileCursor& c) {
+        if (c.valid && ++c.pair == c.npairs) {
+            c.t += w.step;
+            enter_tile(c);
+        }
+    };
+    int node_n[2][2];
+    uint2 mp_n[2];
+    auto load_idx = [&](const TileCursor& c) {
+#pragma unroll
+        for (int ci = 0; ci < 2; ++ci) {
+            const int at = (c.cp0 + 2 * c.pair + ci) * 16;
+            node_n[ci][0] = buf_i32(rC, (at + r8) * 4);
+            node_n[ci][1] = buf_i32(rC, (at + 8 + r8) * 4);
+            const u32x2 m2 = __builtin_amdgcn_raw_buffer_load_b64(rM, (at + j) * 32 + 8 * g, 0, 0);
+            mp_n[ci] = make_uint2(m2.x, m2.y);
+        }
+    };
+    Row<bf16_t> kr[2][2], vr[2][2];   // [chunk][half of its rows]: this lane's 16-byte piece
+    bf16x8_t qn0, qn1;                // Q^T operand of the tile whose first pair is in flight
+    auto request_rows = [&](const TileCursor& c) {
+        const int64_t base = (int64_t)(c.bh / a.H) * a.sb + (int64_t)(c.bh % a.H) * a.sh;
+        const rsrc_t rK = make_rsrc(a.K + base, a.slab_bytes), rV = make_rsrc(a.V + base, a.slab_bytes);
+#pragma unroll
+        for (int ci = 0; ci < 2; ++ci)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int off = (int)__umul24(node_n[ci][h], a.row_bytes) + piece * 16;
+                buf_row(rK, off, kr[ci][h]);
+                buf_row(rV, off, vr[ci][h]);
+            }
+        if (c.pair == 0) {   // token j, features 16g..16g+15
+            const int64_t at = base + (int64_t)(c.tile * 16 + j) * a.sn + 16 * g;
+            qn0 = *reinterpret_cast<const bf16x8_t*>(a.Q + at);
+            qn1 = *reinterpret_cast<const bf16x8_t*>(a.Q + at + 8);
+        }
+    };
+
+    TileCursor cc, cr, ci;
+    cc.t = w.t;
+    enter_tile(cc);
+    if (!cc.valid) return;
+    load_idx(cc);
+    request_rows(cc);
+    uint2 mp[2] = {mp_n[0], mp_n[1]};
+    cr = cc;
+    advance(cr);
+    if (cr.valid) load_idx(cr);
+    ci = cr;
+    advance(ci);
+
+    bf16x8_t qb0, qb1;
+    float m_run = kNegBig, l_part = 0.f;
+    f32x4_t o[4];
+
+    while (cc.valid) {
+        if (cc.pair == 0) {   // a new tile: its Q rows arrived with the rows of this pair
+            qb0 = qn0;
+            qb1 = qn1;
+            m_run = kNegBig;
+            l_part = 0.f;
+#pragma unroll
+            for (int f = 0; f < 4; ++f) o[f] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            // bias^T = Rel x Q^T, kept in LDS as [token][compact id]
+            for (int c = 0; c < a.cid_pad; c += 16) {
+                bf16x8_t r0, r1;
+                if (REL_LDS) {
+                    const bf16_t* rrow = rel_s + (c + j) * kRelStride + 16 * g;
+                    r0 = *reinterpret_cast<const bf16x8_t*>(rrow);
+                    r1 = *reinterpret_cast<const bf16x8_t*>(rrow + 8);
+                } else {   // padding ids repeat the last real one; no column carries them
+                    const bf16_t* rrow = a.rel + (int64_t)a.cid_to_id[min(c + j, a.num_cids - 1)] * kD + 16 * g;
+                    r0 = *reinterpret_cast<const bf16x8_t*>(rrow);
+                    r1 = *reinterpret_cast<const bf16x8_t*>(rrow + 8);
+                }
+                f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r0, qb0, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r1, qb1, acc, 0, 0, 0);
+                *reinterpret_cast<f32x4_t*>(bias_s + j * a.bias_stride + c + 4 * g) = acc;
+            }
+        }
+        wave_lds_sync();  // the previous pair's reads of k_s, v_s (and the previous tile's of bias_s) are done
+#pragma unroll
+        for (int ci2 = 0; ci2 < 2; ++ci2)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int row = 16 * ci2 + 8 * h + r8;
+                *reinterpret_cast<uint4*>(k_s + row * kRowStride + piece * 8) = kr[ci2][h].w;
+                *reinterpret_cast<uint4*>(v_s + row * kRowStride + piece * 8) = vr[ci2][h].w;
+            }
+        __builtin_amdgcn_sched_barrier(0);
+        // the row registers are free: request the next pair's rows, then the ids of the pair after it
+        const uint2 mpc[2] = {mp[0], mp[1]};
+        if (cr.valid) {
+            request_rows(cr);
+            mp[0] = mp_n[0];
+            mp[1] = mp_n[1];
+        }
+        if (ci.valid) load_idx(ci);
+        __builtin_amdgcn_sched_barrier(0);
+        wave_lds_sync();
+
+        int cid[2][4];
+        float bv[2][4];
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            cid[c][0] = (int)(short)(mpc[c].x & 0xFFFFu);
+            cid[c][1] = (int)(short)(mpc[c].x >> 16);
+            cid[c][2] = (int)(short)(mpc[c].y & 0xFFFFu);
+            cid[c][3] = (int)(short)(mpc[c].y >> 16);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) bv[c][r] = bias_s[j * a.bias_stride + max(cid[c][r], 0)];
+        }
+        f32x4_t s4[2];
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const bf16_t* krow = k_s + (16 * c + j) * kRowStride + 16 * g;
+            s4[c] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            s4[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(krow), qb0, s4[c], 0, 0, 0);
+            s4[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(krow + 8), qb1, s4[c], 0, 0, 0);
+        }
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) asm volatile("" : "+v"(bv[c][r]));  // reads stay out of branches on the mask
+        // online softmax over the pair's 32 columns
+        float sc[2][4], gm = kNegBig;
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                sc[c][r] = cid[c][r] >= 0 ? (s4[c][r] + bv[c][r]) * qscale : kNegBig;
+                gm = fmaxf(gm, sc[c][r]);
+            }
+        gm = fmaxf(gm, __shfl_xor(gm, 16));
+        gm = fmaxf(gm, __shfl_xor(gm, 32));
+        const float mn = fmaxf(m_run, gm);
+        const float corr = fast_exp2(m_run - mn);
+        m_run = mn;
+        float psum = 0.f;
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float p = sc[c][r] > 0.5f * kNegBig ? fast_exp2(sc[c][r] - mn) : 0.f;
+                sc[c][r] = p;
+                psum += p;
+            }
+        l_part = l_part * corr + psum;
+        // the accumulators hold tokens 4g..4g+3: fetch their correction factors
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float cr4 = __shfl(corr, 4 * g + r);
+#pragma unroll
+            for (int f = 0; f < 4; ++f) o[f][r] *= cr4;
+        }
+        u32x4 pa;
+        pa.x = pack_bf16(sc[0][0], sc[0][1]);
+        pa.y = pack_bf16(sc[0][2], sc[0][3]);
+        pa.z = pack_bf16(sc[1][0], sc[1][1]);
+        pa.w = pack_bf16(sc[1][2], sc[1][3]);
+        const bf16x8_t pA = __builtin_bit_cast(bf16x8_t, pa);
+#pragma unroll
+        for (int f = 0; f < 4; ++f)
+            o[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pA, lds_transposed_b(v_s, kRowStride, f, g, j), o[f], 0, 0, 0);
+
+        if (cc.pair == cc.npairs - 1) {   // the tile is complete
+            const int64_t base = (int64_t)(cc.bh / a.H) * a.sb + (int64_t)(cc.bh % a.H) * a.sh;
+            const int t0 = cc.tile * 16;
+            // row sums: token j is spread over the 4 lane groups
+            float l = l_part + __shfl_xor(l_part, 16);
+            l += __shfl_xor(l, 32);
+            if (g == 0) a.lse[(int64_t)cc.bh * a.N + t0 + j] = (m_run + fast_log2(l)) * kLn2;
+            bf16_t* orow = a.out + base + (int64_t)t0 * a.sn + j;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float inv = 1.f / __shfl(l, 4 * g + r);
+#pragma unroll
+                for (int f = 0; f < 4; ++f)
+                    orow[(int64_t)(4 * g + r) * a.sn + 16 * f] = (bf16_t)to_bf16_bits(o[f][r] * inv);
+            }
+        }
+        cc = cr;
+        cr = ci;
+        advance(ci);
+    }
+}
+
+
+// ---- backward, query side, over the same dense tiles (bf16) --------------------------
+// Per tile: S^T and dP^T = V_chunk x dO^T on the matrix cores, p = exp2(s - lse),
+// w = p dP, delta = sum w; then, with K staged in LDS as the B operand,
+//   dQ_K = scale * (W K_U - delta * P K_U)       (the key part of dQ; lse is known, so
+// no online softmax and no second pass).  (w, p) of every edge goes to `wp` in CSR
+// order for the d_rel kernel, which also adds the relative-position part of dQ.
+// REL_LDS: the compact relative-position table is staged in LDS; otherwise (large tables) its rows
+// are read from memory when a tile forms its bias table.
+template <bool REL_LDS>
+__global__ void __launch_bounds__(kTileThreads, 2) bwd_q_tile_kernel(const TileArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    bf16_t* rel_s = reinterpret_cast<bf16_t*>(smem);
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int g = lane >> 4, j = lane & 15;
+    const int r8 = lane >> 3, piece = lane & 7;   // coalesced row fetches: row of the instruction, 16-byte piece
+    const size_t rel_bytes = REL_LDS ? (size_t)a.cid_pad * kRelStride * sizeof(bf16_t) : 0;
+    float* bias_s = reinterpret_cast<float*>(smem + rel_bytes) +
+                    (size_t)wave * 16 * a.bias_stride;
+    bf16_t* k_s = reinterpret_cast<bf16_t*>(smem + rel_bytes + (size_t)kTileWaves * 16 * a.bias_stride * sizeof(float)) +
+                  (size_t)wave * 64 * kRowStride;                      // [32 columns][kRowStride]: K rows
+    bf16_t* v_s = k_s + 32 * kRowStride;                                // the same for V rows
+    if (REL_LDS) {
+        for (int i = threadIdx.x; i < a.cid_pad * 8; i += blockDim.x) {
+            const int cid = i >> 3, c8 = (i & 7) * 8;
+            uint4 w = make_uint4(0u, 0u, 0u, 0u);
+            if (cid < a.num_cids) w = *reinterpret_cast<const uint4*>(a.rel + (int64_t)a.cid_to_id[cid] * kD + c8);
+            *reinterpret_cast<uint4*>(rel_s + cid * kRelStride + c8) = w;
+        }
+    }
+    __syncthreads();
+
+    const float qscale = a.scale * kLog2e;
+    const rsrc_t rC = make_rsrc(a.cols, (uint32_t)a.num_chunks * 64u);
+    const rsrc_t rM = make_rsrc(a.map, (uint32_t)a.num_chunks * 512u);
+    const int groups_per_bh = (a.num_tiles + kTileWaves - 1) / kTileWaves;
+    const TileWalk w(a.BH * groups_per_bh);
+
+    // The wavefront's work is one sequence of pairs of chunks running through its tiles.
+    // Three positions move along it: `cc` is computed, the rows of `cr` (one pair ahead) are
+    // in flight, the column ids and map words of `ci` (two pairs ahead) are in flight.
+    auto enter_tile = [&](TileCursor& c) {
+        c.valid = false;
+        c.pair = 0;
+        c.npairs = 1;
+        for (; c.t < w.t_end; c.t += w.step) {
+            c.bh = c.t / groups_per_bh;
+            c.tile = (c.t - c.bh * groups_per_bh) * kTileWaves + wave;
+            if (c.tile < a.num_tiles) {
+                c.cp0 = a.chunk_ptr[c.tile];
+                c.npairs = (a.chunk_ptr[c.tile + 1] - c.cp0) >> 1;
+                c.valid = true;
+                return;
+            }
+        }
+    };
+    auto advance = [&](TileCursor& c) {
+        if (c.valid && ++c.pair == c.npairs) {
+            c.t += w.step;
+            enter_tile(c);
+        }
+    };
+    int node_n[2][2];
+    uint2 mp_n[2];
+    auto load_idx = [&](const TileCursor& c) {
+#pragma unroll
+        for (int ci = 0; ci < 2; ++ci) {
+            const int at = (c.cp0 + 2 * c.pair + ci) * 16;
+            node_n[ci][0] = buf_i32(rC, (at + r8) * 4);
+            node_n[ci][1] = buf_i32(rC, (at + 8 + r8) * 4);
+            const u32x2 m2 = __builtin_amdgcn_raw_buffer_load_b64(rM, (at + j) * 32 + 8 * g, 0, 0);
+            mp_n[ci] = make_uint2(m2.x, m2.y);
+        }
+    };
+    Row<bf16_t> kr[2][2], vr[2][2];   // [chunk][half of its rows]: this lane's 16-byte piece
+    bf16x8_t qn0, qn1, gn0, gn1;      // operands of the tile whose first pair is in flight
+    float lse_n = 0.f;
+    auto request_rows = [&](const TileCursor& c) {
+        const int64_t base = (int64_t)(c.bh / a.H) * a.sb + (int64_t)(c.bh % a.H) * a.sh;
+        const rsrc_t rK = make_rsrc(a.K + base, a.slab_bytes), rV = make_rsrc(a.V + base, a.slab_bytes);
+#pragma unroll
+        for (int ci = 0; ci < 2; ++ci)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int off = (int)__umul24(node_n[ci][h], a.row_bytes) + piece * 16;
+                buf_row(rK, off, kr[ci][h]);
+                buf_row(rV, off, vr[ci][h]);
+            }
+        if (c.pair == 0) {   // the tile's own rows: Q^T and dO^T operands (token j, features 16g..16g+15)
+            const int64_t at = base + (int64_t)(c.tile * 16 + j) * a.sn + 16 * g;
+            qn0 = *reinterpret_cast<const bf16x8_t*>(a.Q + at);
+            qn1 = *reinterpret_cast<const bf16x8_t*>(a.Q + at + 8);
+            gn0 = *reinterpret_cast<const bf16x8_t*>(a.dout + at);
+            gn1 = *reinterpret_cast<const bf16x8_t*>(a.dout + at + 8);
+            lse_n = a.lse_r[(int64_t)c.bh * a.N + c.tile * 16 + j];
+        }
+    };
+
+    TileCursor cc, cr, ci;
+    cc.t = w.t;
+    enter_tile(cc);
+    if (!cc.valid) return;
+    load_idx(cc);
+    request_rows(cc);
+    uint2 mp[2] = {mp_n[0], mp_n[1]};
+    cr = cc;
+    advance(cr);
+    if (cr.valid) load_idx(cr);
+    ci = cr;
+    advance(ci);
+
+    bf16x8_t qb0, qb1, gb0, gb1;
+    float lse2 = 0.f, dl_part = 0.f;
+    float2* wp_t = a.wp;   // this (batch, head)'s pairs, in tile order: [chunk][token][16 columns]
+    f32x4_t ow[4], op[4];
+
+    while (cc.valid) {
+        if (cc.pair == 0) {   // a new tile: its operands arrived with the rows of this pair
+            qb0 = qn0; qb1 = qn1; gb0 = gn0; gb1 = gn1;
+            lse2 = lse_n * kLog2e;
+            wp_t = a.wp + (int64_t)cc.bh * a.num_chunks * 256;
+            dl_part = 0.f;
+#pragma unroll
+            for (int f = 0; f < 4; ++f) ow[f] = op[f] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            // bias^T = Rel x Q^T, kept in LDS as [token][compact id]
+            for (int c = 0; c < a.cid_pad; c += 16) {
+                bf16x8_t r0, r1;
+                if (REL_LDS) {
+                    const bf16_t* rrow = rel_s + (c + j) * kRelStride + 16 * g;
+                    r0 = *reinterpret_cast<const bf16x8_t*>(rrow);
+                    r1 = *reinterpret_cast<const bf16x8_t*>(rrow + 8);
+                } else {   // padding ids repeat the last real one; no column carries them
+                    const bf16_t* rrow = a.rel + (int64_t)a.cid_to_id[min(c + j, a.num_cids - 1)] * kD + 16 * g;
+                    r0 = *reinterpret_cast<const bf16x8_t*>(rrow);
+                    r1 = *reinterpret_cast<const bf16x8_t*>(rrow + 8);
+                }
+                f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r0, qb0, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r1, qb1, acc, 0, 0, 0);
+                *reinterpret_cast<f32x4_t*>(bias_s + j * a.bias_stride + c + 4 * g) = acc;
+            }
+        }
+        wave_lds_sync();  // the previous pair's reads of k_s, v_s (and the previous tile's of bias_s) are done
+#pragma unroll
+        for (int ci2 = 0; ci2 < 2; ++ci2)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int row = 16 * ci2 + 8 * h + r8;
+                *reinterpret_cast<uint4*>(k_s + row * kRowStride + piece * 8) = kr[ci2][h].w;
+                *reinterpret_cast<uint4*>(v_s + row * kRowStride + piece * 8) = vr[ci2][h].w;
+            }
+        __builtin_amdgcn_sched_barrier(0);
+        // the row registers are free: request the next pair's rows, then the ids of the pair after it
+        const uint2 mpc[2] = {mp[0], mp[1]};
+        if (cr.valid) {
+            request_rows(cr);
+            mp[0] = mp_n[0]; mp[1] = mp_n[1];
+        }
+        if (ci.valid) load_idx(ci);
+        __builtin_amdgcn_sched_barrier(0);
+        wave_lds_sync();
+
+        // scores and dP of the pair, the relative-position terms read unconditionally
+        int cid[2][4];
+        float bv[2][4];
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            cid[c][0] = (int)(short)(mpc[c].x & 0xFFFFu);
+            cid[c][1] = (int)(short)(mpc[c].x >> 16);
+            cid[c][2] = (int)(short)(mpc[c].y & 0xFFFFu);
+            cid[c][3] = (int)(short)(mpc[c].y >> 16);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) bv[c][r] = bias_s[j * a.bias_stride + max(cid[c][r], 0)];
+        }
+        f32x4_t s4[2], d4[2];
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const bf16_t* krow = k_s + (16 * c + j) * kRowStride + 16 * g;
+            const bf16_t* vrow = v_s + (16 * c + j) * kRowStride + 16 * g;
+            s4[c] = d4[c] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            s4[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(krow), qb0, s4[c], 0, 0, 0);
+            s4[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(krow + 8), qb1, s4[c], 0, 0, 0);
+            d4[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(vrow), gb0, d4[c], 0, 0, 0);
+            d4[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(vrow + 8), gb1, d4[c], 0, 0, 0);
+        }
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) asm volatile("" : "+v"(bv[c][r]));  // reads stay out of branches on the mask
+        float pw[2][4], pp[2][4];
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float p = cid[c][r] >= 0 ? fast_exp2((s4[c][r] + bv[c][r]) * qscale - lse2) : 0.f;
+                const float wgt = p * d4[c][r];
+                dl_part += wgt;
+                pw[c][r] = wgt;
+                pp[c][r] = p;
+            }
+            // (w, p) of this lane's 4 columns: 32 contiguous bytes, a chunk is 2 KB contiguous
+            float4* dst = reinterpret_cast<float4*>(wp_t + ((int64_t)(cc.cp0 + 2 * cc.pair + c) * 16 + j) * 16 + 4 * g);
+            dst[0] = make_float4(pw[c][0], pp[c][0], pw[c][1], pp[c][1]);
+            dst[1] = make_float4(pw[c][2], pp[c][2], pw[c][3], pp[c][3]);
+        }
+        // W and P as A operands, each split into bf16 hi + lo: A - delta*Bv cancels when a
+        // row's softmax is peaked, so the two products need more than 8 mantissa bits
+        uint32_t whi[4], wlo[4], phi[4], plo[4];
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            split_pack(pw[c][0], pw[c][1], whi[2 * c], wlo[2 * c]);
+            split_pack(pw[c][2], pw[c][3], whi[2 * c + 1], wlo[2 * c + 1]);
+            split_pack(pp[c][0], pp[c][1], phi[2 * c], plo[2 * c]);
+            split_pack(pp[c][2], pp[c][3], phi[2 * c + 1], plo[2 * c + 1]);
+        }
+        const u32x4 wh = {whi[0], whi[1], whi[2], whi[3]}, wl = {wlo[0], wlo[1], wlo[2], wlo[3]};
+        const u32x4 ph = {phi[0], phi[1], phi[2], phi[3]}, pl = {plo[0], plo[1], plo[2], plo[3]};
+        const bf16x8_t wH = __builtin_bit_cast(bf16x8_t, wh), wL = __builtin_bit_cast(bf16x8_t, wl);
+        const bf16x8_t pH = __builtin_bit_cast(bf16x8_t, ph), pL = __builtin_bit_cast(bf16x8_t, pl);
+#pragma unroll
+        for (int f = 0; f < 4; ++f) {
+            const bf16x8_t kB = lds_transposed_b(k_s, kRowStride, f, g, j);
+            ow[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wH, kB, ow[f], 0, 0, 0);
+            ow[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wL, kB, ow[f], 0, 0, 0);
+            op[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pH, kB, op[f], 0, 0, 0);
+            op[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pL, kB, op[f], 0, 0, 0);
+        }
+        if (cc.pair == cc.npairs - 1) {   // the tile is complete
+            const int64_t base = (int64_t)(cc.bh / a.H) * a.sb + (int64_t)(cc.bh % a.H) * a.sh;
+            const int t0 = cc.tile * 16;
+            float delta = dl_part + __shfl_xor(dl_part, 16);
+            delta += __shfl_xor(delta, 32);
+            if (g == 0) a.stat[(int64_t)cc.bh * a.N + t0 + j] = make_float2(lse2, delta);
+            float* qrow_out = a.dQ + base + (int64_t)t0 * a.sn + j;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float dr = __shfl(delta, 4 * g + r);
+#pragma unroll
+                for (int f = 0; f < 4; ++f)
+                    qrow_out[(int64_t)(4 * g + r) * a.sn + 16 * f] = a.scale * (ow[f][r] - dr * op[f][r]);
+            }
+        }
+        cc = cr;
+        cr = ci;
+        advance(ci);
+    }
+}
+
+
+// d_rel and the relative-position part of dQ over the token tiles' compact ids (bf16
+// tensors, at most 256 ids in use).  Per block of 32 token rows the workgroup builds
+// DS^T[id][row] (hi and lo halves) in LDS from the (w, p) pairs of the query side: every
+// edge of a token row carries a 16-bit code = compact id * 32 + row % 32 (tile metadata),
+// so an edge needs no search for its row and no lookup of its id.  Q rows are staged
+// row-major and enter the products through transposing LDS reads:
+//   d_rel[id][f] += DS^T (A, 16-byte rows) x Q (B, transposed read),
+//   dQ[row][f]   += scale * DS (A, transposed read of DS^T) x Rel (B, transposed read).
+// Wavefront w owns id chunks w and w + 8; its accumulators live across the blocks the
+// workgroup walks and are written once, as this workgroup's copy, in compact-id order.
+struct RelGradArgs {
+    const bf16_t *Q, *rel;
+    float* dQ;
+    const float2 *stat, *wp;
+    float* drel_part;
+    const int32_t *chunk_ptr, *cid_to_id;
+    const int16_t* map;
+    int64_t sb, sh, sn;
+    int32_t BH, H, N, n, num_tiles, num_chunks, num_cids, nids;   // nids = ids padded to 32
+    float scale;
+};
+// 8 consecutive k of the operand row/column `col0 + j`: two transposing reads of 4 rows each
+__device__ __forceinline__ bf16x8_t lds_tr8(const bf16_t* base, int stride, int row0, int col0, int j) {
+    typedef __attribute__((address_space(3))) s16x4_t* lds_ptr_t;
+    const bf16_t* p = base + (row0 + (j >> 2)) * stride + col0 + 4 * (j & 3);
+    const s16x4_t x = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)p);
+    const s16x4_t y = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p + 4 * stride));
+    typedef short s16x8_t __attribute__((ext_vector_type(8)));
+    const s16x8_t xy = {x[0], x[1], x[2], x[3], y[0], y[1], y[2], y[3]};
+    return __builtin_bit_cast(bf16x8_t, xy);
+}
+
+constexpr int kRgPrefetch = 8;   // tile slots per thread fetched one block ahead (512 threads: 16 chunks)
+constexpr int kRgTileMaxIds = 512;
+// CPW: 16-id chunks per wavefront (2: up to 256 ids, 4: up to 512)
+template <int CPW>
+__global__ void __launch_bounds__(kThreads) rel_grad_tile_kernel(const RelGradArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int nids = a.nids;
+    bf16_t* ds_hi = reinterpret_cast<bf16_t*>(smem);                 // [nids][kRgStride]: DS^T, rows of the block along a line
+    bf16_t* ds_lo = ds_hi + nids * kRgStride;
+    bf16_t* q_s = ds_lo + nids * kRgStride;                          // [32 rows][kRowStride]
+    bf16_t* rel_s = q_s + kRgRows * kRowStride;                      // [nids][kRelStride], compact order
+    __shared__ float delta_s[kRgRows];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int g = lane >> 4, j = lane & 15;
+    for (int i = threadIdx.x; i < nids * 8; i += blockDim.x) {
+        const int cid = i >> 3, c8 = (i & 7) * 8;
+        uint4 w = make_uint4(0u, 0u, 0u, 0u);
+        if (cid < a.num_cids) w = *reinterpret_cast<const uint4*>(a.rel + (int64_t)a.cid_to_id[cid] * kD + c8);
+        *reinterpret_cast<uint4*>(rel_s + cid * kRelStride + c8) = w;
+    }
+    const int blocks_per_bh = (a.n + kRgRows - 1) / kRgRows;
+    const int total = a.BH * blocks_per_bh;
+    const int nchunks = nids >> 4;
+    const rsrc_t rMap = make_rsrc(a.map, (uint32_t)a.num_chunks * 512u);
+
+    f32x4_t acc[CPW][4];
+#pragma unroll
+    for (int c = 0; c < CPW; ++c)
+#pragma unroll
+        for (int f = 0; f < 4; ++f) acc[c][f] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    // What a block needs from memory is requested one block ahead, so that it arrives while
+    // the current block's products run: the thread's piece of a Q row (or a delta), and its
+    // first kRgPrefetch tile slots (compact id from the tile map, (w, p) pair).  The slots of
+    // the block's two token tiles are contiguous: [chunk][token][16 columns].
+    uint4 qpiece = make_uint4(0u, 0u, 0u, 0u);
+    float dl_own = 0.f;
+    int code[kRgPrefetch];
+    float2 wpv[kRgPrefetch];
+    int s_begin = 0, s_mid = 0, s_end = 0;   // first slot of the block, of its second tile, and the end
+    auto prefetch = [&](int blk) {
+        const int bh = blk / blocks_per_bh, b2 = 2 * (blk - bh * blocks_per_bh), row0 = 16 * b2;
+        const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
+        s_begin = a.chunk_ptr[b2] * 256;
+        s_mid = a.chunk_ptr[min(b2 + 1, a.num_tiles)] * 256;
+        s_end = a.chunk_ptr[min(b2 + 2, a.num_tiles)] * 256;
+        qpiece = make_uint4(0u, 0u, 0u, 0u);
+        if (threadIdx.x < kRgRows * 8) {
+            const int r = threadIdx.x >> 3, c = (threadIdx.x & 7) * 8;
+            if (row0 + r < a.n) qpiece = *reinterpret_cast<const uint4*>(a.Q + base + (int64_t)(row0 + r) * a.sn + c);
+        } else if (threadIdx.x < kRgRows * 8 + kRgRows) {
+            const int r = threadIdx.x - kRgRows * 8;
+            dl_own = row0 + r < a.n ? a.stat[(int64_t)bh * a.N + row0 + r].y : 0.f;
+        }
+        const rsrc_t rWp = make_rsrc(a.wp + (int64_t)bh * a.num_chunks * 256, (uint32_t)a.num_chunks * 2048u);
+#pragma unroll
+        for (int k = 0; k < kRgPrefetch; ++k) {
+            const int sl = s_begin + (int)threadIdx.x + k * kThreads;
+            const uint32_t off = sl < s_end ? (uint32_t)sl : 0x1FFFFFFFu;   // past the block: an offset outside the buffers
+            code[k] = (int)(short)__builtin_amdgcn_raw_buffer_load_b16(rMap, (int)(off * 2u), 0, 0);
+            wpv[k] = buf_f2(rWp, (int)(off * 8u));
+        }
+    };
+    if ((int)blockIdx.x < total) prefetch(blockIdx.x);
+
+    for (int blk = blockIdx.x; blk < total; blk += gridDim.x) {
+        const int bh = blk / blocks_per_bh, row0 = (blk - bh * blocks_per_bh) * kRgRows;
+        const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
+        // clear DS^T (hi and lo are adjacent), stage the block's Q rows and deltas
+        for (int i = threadIdx.x * 8; i < 2 * nids * kRgStride; i += blockDim.x * 8)
+            *reinterpret_cast<uint4*>(ds_hi + i) = make_uint4(0u, 0u, 0u, 0u);
+        if (threadIdx.x < kRgRows * 8)
+            *reinterpret_cast<uint4*>(q_s + (threadIdx.x >> 3) * kRowStride + (threadIdx.x & 7) * 8) = qpiece;
+        else if (threadIdx.x < kRgRows * 8 + kRgRows)
+            delta_s[threadIdx.x - kRgRows * 8] = dl_own;
+        __syncthreads();
+        // scatter dS = w - delta * p of the block's tile slots, one thread per slot; a masked slot
+        // has the id -1; the row of a slot follows from its position
+        const int cur_begin = s_begin, cur_mid = s_mid, cur_end = s_end;
+        auto scatter = [&](int sl, int cid, float2 x) {
+            if (cid < 0) return;
+            const int r = ((sl >> 4) & 15) + (sl >= cur_mid ? 16 : 0);
+            const float ds = x.x - delta_s[r] * x.y;
+            uint32_t hi, lo;
+            split_pack(ds, 0.f, hi, lo);
+            ds_hi[cid * kRgStride + r] = (bf16_t)hi;
+            ds_lo[cid * kRgStride + r] = (bf16_t)lo;
+        };
+#pragma unroll
+        for (int k = 0; k < kRgPrefetch; ++k) {
+            const int sl = cur_begin + (int)threadIdx.x + k * kThreads;
+            if (sl < cur_end) scatter(sl, code[k], wpv[k]);
+        }
+        {   // blocks with more slots than were fetched ahead
+            const float2* wp_b = a.wp + (int64_t)bh * a.num_chunks * 256;
+            for (int sl = cur_begin + (int)threadIdx.x + kRgPrefetch * kThreads; sl < cur_end; sl += kThreads)
+                scatter(sl, a.map[sl], wp_b[sl]);
+        }
+        // the dQ values this thread will add to, and everything the next block needs
+        const int mc = wave >> 2, fc = wave & 3;
+        float dq_old[4];
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            const int row = row0 + 16 * mc + 4 * g + m;
+            dq_old[m] = row < a.n ? a.dQ[base + (int64_t)row * a.sn + 16 * fc + j] : 0.f;
+        }
+        if (blk + (int)gridDim.x < total) prefetch(blk + gridDim.x);
+        __syncthreads();
+        {   // dQ of the block: wavefront -> 16 rows x 16 features
+            f32x4_t dq = {0.f, 0.f, 0.f, 0.f};
+            for (int ks = 0; ks < nids; ks += 32) {
+                const bf16x8_t rb = lds_tr8(rel_s, kRelStride, ks + 8 * g, 16 * fc, j);
+                dq = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lds_tr8(ds_hi, kRgStride, ks + 8 * g, 16 * mc, j), rb, dq, 0, 0, 0);
+                dq = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lds_tr8(ds_lo, kRgStride, ks + 8 * g, 16 * mc, j), rb, dq, 0, 0, 0);
+            }
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                const int row = row0 + 16 * mc + 4 * g + m;
+                if (row < a.n) a.dQ[base + (int64_t)row * a.sn + 16 * fc + j] = dq_old[m] + a.scale * dq[m];
+            }
+        }
+        bf16x8_t qb[4];
+#pragma unroll
+        for (int f = 0; f < 4; ++f) qb[f] = lds_tr8(q_s, kRowStride, 8 * g, 16 * f, j);
+#pragma unroll
+        for (int c = 0; c < CPW; ++c) {
+            const int chunk = wave + kWaves * c;
+            if (chunk < nchunks) {
+                const int off = (16 * chunk + j) * kRgStride + 8 * g;
+                const bf16x8_t ah = *reinterpret_cast<const bf16x8_t*>(ds_hi + off);
+                const bf16x8_t al = *reinterpret_cast<const bf16x8_t*>(ds_lo + off);
+#pragma unroll
+                for (int f = 0; f < 4; ++f) {
+                    acc[c][f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, qb[f], acc[c][f], 0, 0, 0);
+                    acc[c][f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al, qb[f], acc[c][f], 0, 0, 0);
+                }
+            }
+        }
+        __syncthreads();
+    }
+    // this workgroup's copy: [gridDim.x][nids][kD], compact-id order
+    float* dst = a.drel_part + (int64_t)blockIdx.x * nids * kD;
+#pragma unroll
+    for (int c = 0; c < CPW; ++c) {
+        const int chunk = wave + kWaves * c;
+        if (chunk < nchunks) {
+#pragma unroll
+            for (int f = 0; f < 4; ++f)
+#pragma unroll
+                for (int m = 0; m < 4; ++m) dst[(16 * chunk + 4 * g + m) * kD + 16 * f + j] = acc[c][f][m] * a.scale;
+        }
+    }
+}
+
+}  // namespace
+}  // namespace bpt
