@@ -251,10 +251,26 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyA
     }
 }
 
-// tiles whose query list was cut into several tasks: sum the partial (dK, dV) of the
-// tile's keys in task order.  One workgroup per (batch*head, tile); thread -> (key, feature pair).
+// Tiles whose query list was cut into several tasks: sum the partial (dK, dV) of the
+// tile's keys in task order.  One workgroup per (batch*head, tile); thread -> (key, feature).
+// The workgroups after those write the zero gradients of the nodes no one attends to
+// (levels above the coarsest contextual level, from `first_zero` on).
 __global__ void __launch_bounds__(256) kv_tile_merge_kernel(const KeyArgs a, const int32_t* __restrict__ multi_tile,
-                                                            const int32_t* __restrict__ multi_ptr, int num_multi) {
+                                                            const int32_t* __restrict__ multi_ptr, int num_multi,
+                                                            int first_zero) {
+    const int merge_blocks = a.BH * num_multi;
+    if ((int)blockIdx.x >= merge_blocks) {
+        const int rows = a.N - first_zero;
+        const int64_t i = (int64_t)(blockIdx.x - merge_blocks) * blockDim.x + threadIdx.x;
+        if (i >= (int64_t)a.BH * rows * kD) return;
+        const int f = (int)(i & 63);
+        const int64_t rr = i >> 6;
+        const int bh = (int)(rr / rows), row = first_zero + (int)(rr - (int64_t)bh * rows);
+        const int64_t at = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh + (int64_t)row * a.sn + f;
+        a.dK[at] = 0.f;
+        a.dV[at] = 0.f;
+        return;
+    }
     const int bh = blockIdx.x / num_multi, mt = blockIdx.x - bh * num_multi;
     const int kt = multi_tile[mt];
     const int node0 = a.tile_node0[kt], nkeys = a.tile_info[kt] >> 8;
@@ -271,19 +287,6 @@ __global__ void __launch_bounds__(256) kv_tile_merge_kernel(const KeyArgs a, con
         a.dK[at] = sk;
         a.dV[at] = sv;
     }
-}
-
-// nodes no one attends to (levels above the coarsest contextual level): zero gradients
-__global__ void kv_zero_rows_kernel(const KeyArgs a, int first_row) {
-    const int rows = a.N - first_row;
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= (int64_t)a.BH * rows * kD) return;
-    const int f = (int)(i & 63);
-    const int64_t rr = i >> 6;
-    const int bh = (int)(rr / rows), row = first_row + (int)(rr - (int64_t)bh * rows);
-    const int64_t at = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh + (int64_t)row * a.sn + f;
-    a.dK[at] = 0.f;
-    a.dV[at] = 0.f;
 }
 
 // key nodes cut into several segments: sum the (dK, dV) partials in segment order

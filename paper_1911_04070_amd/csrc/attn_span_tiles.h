@@ -214,10 +214,10 @@ __device__ __forceinline__ bool span_merge_row(const SpanArgs& a, int item, int 
     return true;
 }
 
-__global__ void __launch_bounds__(256) fwd_span_merge_small_kernel(const SpanArgs a, int first, int rows) {
+__device__ __forceinline__ void fwd_span_merge_small(const SpanArgs& a, int item, int first, int rows) {
     const int lane = threadIdx.x & 63;
     SpanRow r;
-    if (!span_merge_row(a, blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6), first, rows, kPartStride, r)) return;
+    if (!span_merge_row(a, item, first, rows, kPartStride, r)) return;
     float o[kSpanSmallMax], m[kSpanSmallMax], l[kSpanSmallMax];
 #pragma unroll
     for (int b = 0; b < kSpanSmallMax; ++b) {
@@ -241,12 +241,19 @@ __global__ void __launch_bounds__(256) fwd_span_merge_small_kernel(const SpanArg
     if (lane == 0) a.lse[(int64_t)r.bh * a.N + r.v] = (mx + fast_log2(ls)) * kLn2;
 }
 
-__global__ void __launch_bounds__(kSpanBigThreads) fwd_span_merge_big_kernel(const SpanArgs a, int first, int rows) {
+// one kernel for both kinds of rows: the first `small_blocks` workgroups take 16 short rows each
+// (one per wavefront), the others one long row each
+__global__ void __launch_bounds__(kSpanBigThreads) fwd_span_merge_kernel(const SpanArgs a, int first, int rows_small,
+                                                                         int first_big, int rows_big, int small_blocks) {
     __shared__ float s_acc[64][kD + 4];
     __shared__ float s_l[64];
     __shared__ float s_m[kSpanBigThreads / 64];
+    if ((int)blockIdx.x < small_blocks) {   // uniform for the workgroup; this path has no barrier
+        fwd_span_merge_small(a, blockIdx.x * (kSpanBigThreads / 64) + (threadIdx.x >> 6), first, rows_small);
+        return;
+    }
     SpanRow r;
-    if (!span_merge_row(a, blockIdx.x, first, rows, kPartStride, r)) return;   // uniform for the workgroup
+    if (!span_merge_row(a, blockIdx.x - small_blocks, first_big, rows_big, kPartStride, r)) return;   // uniform for the workgroup
     const int t = threadIdx.x, fq = t & 15, pl = t >> 4;
     float mx = kNegBig;
     for (int b = t; b < r.cnt; b += kSpanBigThreads) mx = fmaxf(mx, r.src[(int64_t)b * kPartStride + 64]);
@@ -421,10 +428,10 @@ __global__ void __launch_bounds__(kTileThreads) bwd_q_span_tile_kernel(const Spa
     }
 }
 
-__global__ void __launch_bounds__(256) bwd_q_span_merge_small_kernel(const SpanArgs a, int first, int rows) {
+__device__ __forceinline__ void bwd_q_span_merge_small(const SpanArgs& a, int item, int first, int rows) {
     const int lane = threadIdx.x & 63;
     SpanRow r;
-    if (!span_merge_row(a, blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6), first, rows, kQPartStride, r)) return;
+    if (!span_merge_row(a, item, first, rows, kQPartStride, r)) return;
     float xa[kSpanSmallMax], xb[kSpanSmallMax], xd[kSpanSmallMax];
 #pragma unroll
     for (int b = 0; b < kSpanSmallMax; ++b) {
@@ -446,11 +453,16 @@ __global__ void __launch_bounds__(256) bwd_q_span_merge_small_kernel(const SpanA
     if (lane == 0) a.stat[(int64_t)r.bh * a.N + r.v] = make_float2(a.lse_r[(int64_t)r.bh * a.N + r.v] * kLog2e, dl);
 }
 
-__global__ void __launch_bounds__(kSpanBigThreads) bwd_q_span_merge_big_kernel(const SpanArgs a, int first, int rows) {
+__global__ void __launch_bounds__(kSpanBigThreads) bwd_q_span_merge_kernel(const SpanArgs a, int first, int rows_small,
+                                                                           int first_big, int rows_big, int small_blocks) {
     __shared__ float s_a[64][kD + 4], s_b[64][kD + 4];
     __shared__ float s_d[64];
+    if ((int)blockIdx.x < small_blocks) {
+        bwd_q_span_merge_small(a, blockIdx.x * (kSpanBigThreads / 64) + (threadIdx.x >> 6), first, rows_small);
+        return;
+    }
     SpanRow r;
-    if (!span_merge_row(a, blockIdx.x, first, rows, kQPartStride, r)) return;
+    if (!span_merge_row(a, blockIdx.x - small_blocks, first_big, rows_big, kQPartStride, r)) return;
     const int t = threadIdx.x, fq = t & 15, pl = t >> 4;
     float4 sa = make_float4(0.f, 0.f, 0.f, 0.f), sb = sa;
     float dl = 0.f;

@@ -258,24 +258,16 @@ int run_span_tiles(const bpt_graph* g, const AttnArgs& a, bool forward, hipStrea
         const int big_level = kSpanInLevels + 1 + kSpanSmallLevels;
         const int first_big = t.L >= big_level ? 2 * g->n - ((2 * g->n) >> big_level) : g->num_nodes;
         const int rows_small = first_big - first, rows_big = g->num_nodes - first_big;
-        const unsigned sgrid = (unsigned)(((int64_t)a.BH * rows_small + 3) / 4);
+        const int per_block = kSpanBigThreads / 64;   // short rows per workgroup
+        const int small_blocks = (int)(((int64_t)a.BH * rows_small + per_block - 1) / per_block);
+        const unsigned mgrid = (unsigned)(small_blocks + (int64_t)a.BH * rows_big);
         if (forward)
-            BPT_LAUNCH("fwd_span_merge_small_kernel", fwd_span_merge_small_kernel, dim3(sgrid), dim3(256), 0, st, t, first,
-                       rows_small);
+            BPT_LAUNCH("fwd_span_merge_kernel", fwd_span_merge_kernel, dim3(mgrid), dim3(kSpanBigThreads), 0, st, t, first,
+                       rows_small, first_big, rows_big, small_blocks);
         else
-            BPT_LAUNCH("bwd_q_span_merge_small_kernel", bwd_q_span_merge_small_kernel, dim3(sgrid), dim3(256), 0, st, t,
-                       first, rows_small);
+            BPT_LAUNCH("bwd_q_span_merge_kernel", bwd_q_span_merge_kernel, dim3(mgrid), dim3(kSpanBigThreads), 0, st, t, first,
+                       rows_small, first_big, rows_big, small_blocks);
         BPT_HIP(hipGetLastError());
-        if (rows_big > 0) {
-            const unsigned bgrid = (unsigned)((int64_t)a.BH * rows_big);
-            if (forward)
-                BPT_LAUNCH("fwd_span_merge_big_kernel", fwd_span_merge_big_kernel, dim3(bgrid), dim3(kSpanBigThreads), 0, st,
-                           t, first_big, rows_big);
-            else
-                BPT_LAUNCH("bwd_q_span_merge_big_kernel", bwd_q_span_merge_big_kernel, dim3(bgrid), dim3(kSpanBigThreads), 0,
-                           st, t, first_big, rows_big);
-            BPT_HIP(hipGetLastError());
-        }
     }
     return BPT_OK;
 }
@@ -562,15 +554,11 @@ int run_bwd_kv_tiles(const bpt_graph* g, const BwdPlan& p, const AttnArgs& a, co
         default: break;
     }
     if (rc) return rc;
-    if (kt.num_multi > 0) {
-        BPT_LAUNCH("kv_tile_merge_kernel", kv_tile_merge_kernel, dim3(a.BH * kt.num_multi), dim3(256), 0, st, t, kt.multi_tile,
-                           kt.multi_ptr, kt.num_multi);
-        BPT_HIP(hipGetLastError());
-    }
     const int64_t zero_elems = (int64_t)a.BH * (a.N - kt.first_uncovered) * kD;
-    if (zero_elems > 0) {
-        BPT_LAUNCH("kv_zero_rows_kernel", kv_zero_rows_kernel, dim3((unsigned)((zero_elems + 255) / 256)), dim3(256), 0, st, t,
-                           kt.first_uncovered);
+    const int64_t blocks = (int64_t)a.BH * kt.num_multi + (zero_elems + 255) / 256;
+    if (blocks > 0) {
+        BPT_LAUNCH("kv_tile_merge_kernel", kv_tile_merge_kernel, dim3((unsigned)blocks), dim3(256), 0, st, t, kt.multi_tile,
+                   kt.multi_ptr, kt.num_multi, kt.first_uncovered);
         BPT_HIP(hipGetLastError());
     }
     return BPT_OK;
