@@ -604,6 +604,7 @@ int make_key_tiles(int32_t n, int32_t k, int32_t num_levels, int32_t ctx_levels,
     // tasks
     std::vector<int32_t> task_tile, task_c0, task_nch, task_part, multi_tile, multi_ptr(1, 0);
     int32_t parts = 0;
+    const int32_t kKeyTaskChunks = key_task_chunks(n);
     for (int32_t kt = 0; kt < nkt; ++kt) {
         const int32_t c0 = chunk_ptr[kt], nch = chunk_ptr[kt + 1] - c0;
         const int32_t ntask = std::max(1, (nch + kKeyTaskChunks - 1) / kKeyTaskChunks);

@@ -49,9 +49,11 @@ struct TokenTiles {
 // to 16 consecutive nodes of one level; its columns are the nodes that attend to any
 // of them (tokens on either side, and for token keys their ancestor spans), in
 // ascending node id, in chunks of 16 (an even number per tile).  A tile's chunk list
-// is cut into tasks of at most kKeyTaskChunks chunks; tiles with several tasks are
-// summed by a merge kernel in task order.
-constexpr int kKeyTaskChunks = 32;
+// is cut into tasks of at most key_task_chunks(n) chunks; tiles with several tasks are
+// summed by a merge kernel in task order.  Longer tasks mean fewer partial sums to write and
+// merge (n = 65536: key side 0.67 -> 0.60 ms) but, when a (batch, head) has few tiles, waves
+// that wait for the one with the longest task (n = 512: 0.12 -> 0.29 ms).
+inline int key_task_chunks(int n) { return n >= 16384 ? 64 : 32; }
 struct KeyTiles {
     int32_t num_tasks = 0, num_multi = 0, num_part = 0;
     int32_t num_chunks = 0;         // chunks of all tiles together
