@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libbpt.so")
-SOURCES = ["bpt_graph.hip", "bpt_attn.hip"]
+SOURCES = ["bpt_graph.hip", "bpt_tiles.hip", "bpt_attn.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-munsafe-fp-atomics",
     # packed fp32 VALU forms are kept off on the test machines

@@ -6,8 +6,9 @@
 //   scan_*         exclusive prefix sum -> row_ptr
 //   fill_tokens    one thread per token emits (col, rel) of its row in canonical order
 //   fill_spans     one thread per affiliated edge (closed form)
-//   t_count        per token-row edge: in-degree and first query on each side of the key
+//   t_ranges       first and last query token on each side of every key node (no atomics)
 //   t_fill         closed-form slot of every edge in the transposed adjacency
+// The dense tiles of the matrix-core kernels are built by bpt_tiles.hip.
 #include <algorithm>
 #include <cstdio>
 #include <cstring>
@@ -251,36 +252,70 @@ __global__ void t_init(int num_nodes, int32_t* __restrict__ cnt_l, int32_t* __re
                        int32_t* __restrict__ min_l, int32_t* __restrict__ min_r) {
     int v = blockIdx.x * blockDim.x + threadIdx.x;
     if (v < num_nodes) {
-        cnt_l[v] = 0;
-        cnt_r[v] = 0;
+        cnt_l[v] = -1;  // until t_degree: the last token of the range (t_ranges), -1 = no token
+        cnt_r[v] = -1;
         min_l[v] = INT32_MAX;
         min_r[v] = INT32_MAX;
     }
 }
 
-__global__ void t_count(int n, int k, const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col,
-                        const int32_t* __restrict__ rel, int32_t* __restrict__ cnt_l, int32_t* __restrict__ cnt_r,
-                        int32_t* __restrict__ min_l, int32_t* __restrict__ min_r) {
-    int i = blockIdx.x * blockDim.x + threadIdx.x;
+// First and last token of the range that attends to every node from each side, without
+// atomics: token i is the first of node x's range iff token i-1 does not attend to x at that
+// level, and the last iff token i+1 does not.  One thread per token walks the levels of
+// tokens i-1, i and i+1 together.  `last_*` receive the last token (t_degree turns them into counts).
+__global__ void t_ranges(int n, int k, int causal, int32_t* __restrict__ last_l, int32_t* __restrict__ last_r,
+                         int32_t* __restrict__ min_l, int32_t* __restrict__ min_r) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
-    const int W = 2 * (k + 1) + 1, zero = k + 1;
-    for (int e = row_ptr[i]; e < row_ptr[i + 1]; ++e) {
-        int order = rel[e] % W - zero;
-        int v = col[e];
-        if (order > 0) {  // v lies to the right of token i: i is a query on v's left
-            atomicAdd(&cnt_l[v], 1);
-            atomicMin(&min_l[v], i);
-        } else if (order < 0) {
-            atomicAdd(&cnt_r[v], 1);
-            atomicMin(&min_r[v], i);
+    const bool has_prev = i > 0, has_next = i + 1 < n;
+    {   // nodes in the left context of i: i lies to their right
+        LeftWalk A(i), P(i - 1), N(i + 1);
+        for (int j = 0; A.alive(); ++j) {
+            const int off = (int)level_offset(n, j);
+            int lo, hi, plo = 0, phi = -1, nlo = 0, nhi = -1;
+            A.run(k, lo, hi);
+            const bool pa = has_prev && P.alive(), na = has_next && N.alive();
+            if (pa) P.run(k, plo, phi);
+            if (na) N.run(k, nlo, nhi);
+            for (int x = lo; x <= hi; ++x) {
+                if (!(pa && plo <= x && x <= phi)) min_r[off + x] = i;
+                if (!(na && nlo <= x && x <= nhi)) last_r[off + x] = i;
+            }
+            A.up(lo);
+            if (pa) P.up(plo);
+            if (na) N.up(nlo);
+        }
+    }
+    if (!causal) {   // nodes in the right context of i: i lies to their left
+        RightWalk A(i, n), P(i - 1, n), N(i + 1, n);
+        for (int j = 0; A.alive(); ++j) {
+            const int off = (int)level_offset(n, j);
+            int lo, hi, plo = 0, phi = -1, nlo = 0, nhi = -1;
+            A.run(k, lo, hi);
+            const bool pa = has_prev && P.alive(), na = has_next && N.alive();
+            if (pa) P.run(k, plo, phi);
+            if (na) N.run(k, nlo, nhi);
+            for (int x = lo; x <= hi; ++x) {
+                if (!(pa && plo <= x && x <= phi)) min_l[off + x] = i;
+                if (!(na && nlo <= x && x <= nhi)) last_l[off + x] = i;
+            }
+            A.up(hi);
+            if (pa) P.up(phi);
+            if (na) N.up(nhi);
         }
     }
 }
 
-__global__ void t_degree(int n, int num_nodes, int num_levels, const int32_t* __restrict__ cnt_l,
-                         const int32_t* __restrict__ cnt_r, int32_t* __restrict__ t_deg) {
+// counts from the (first, last) pairs, and the in-degree of every node
+__global__ void t_degree(int n, int num_nodes, int num_levels, int32_t* __restrict__ cnt_l, int32_t* __restrict__ cnt_r,
+                         const int32_t* __restrict__ min_l, const int32_t* __restrict__ min_r,
+                         int32_t* __restrict__ t_deg) {
     int v = blockIdx.x * blockDim.x + threadIdx.x;
-    if (v < num_nodes) t_deg[v] = cnt_l[v] + cnt_r[v] + (v < n ? num_levels : 0);  // self + one per ancestor
+    if (v >= num_nodes) return;
+    const int cl = cnt_l[v] >= 0 ? cnt_l[v] - min_l[v] + 1 : 0, cr = cnt_r[v] >= 0 ? cnt_r[v] - min_r[v] + 1 : 0;
+    cnt_l[v] = cl;
+    cnt_r[v] = cr;
+    t_deg[v] = cl + cr + (v < n ? num_levels : 0);  // self + one per ancestor
 }
 
 __global__ void t_fill_tokens(int n, int k, const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col,
@@ -440,75 +475,8 @@ void free_tiles(TokenTiles& t) {
     t = TokenTiles();
 }
 
-// Tile metadata for the matrix-core kernels, from the token rows of the CSR.  The
-// key nodes of 16 consecutive token rows are bucketed by (level, side); inside a
-// bucket the union is taken as the node range [min, max] (a node in the range that
-// no row attends to is just a masked column), so a column's slot follows from the
-// bucket's first slot and first node.  Buckets are laid out by level, left before
-// right, i.e. in ascending node id.
-int make_token_tiles(int32_t n, int32_t k, int32_t num_levels, const std::vector<int32_t>& ptr,
-                     const std::vector<int32_t>& col, const std::vector<int32_t>& rel, TokenTiles& out) {
-    const int32_t tiles = n / 16, W = 2 * (k + 1) + 1, zero = k + 1, num_ids = num_levels * W;
-    const int32_t nb = 2 * num_levels;  // bucket 0: level 0; 2l-1 / 2l: left / right of level l
-    std::vector<int32_t> cid(num_ids, -1), cid_to_id;
-    for (int32_t e = 0; e < ptr[n]; ++e) cid[rel[e]] = 0;
-    for (int32_t id = 0; id < num_ids; ++id)
-        if (cid[id] == 0) {
-            cid[id] = (int32_t)cid_to_id.size();
-            cid_to_id.push_back(id);
-        }
-    if (cid_to_id.size() > 32767) return BPT_OK;  // ids would not fit the 16-bit maps: no tile path
-    auto bucket_of = [&](int32_t r) {
-        const int32_t lev = r / W, ord = r % W - zero;
-        return lev == 0 ? 0 : 2 * lev - 1 + (ord > 0 ? 1 : 0);
-    };
-    std::vector<int32_t> chunk_ptr(1, 0), cols, lo(nb), hi(nb), first(nb);
-    std::vector<int16_t> map;
-    for (int32_t t = 0; t < tiles; ++t) {
-        std::fill(lo.begin(), lo.end(), INT32_MAX);
-        std::fill(hi.begin(), hi.end(), -1);
-        const int32_t b = ptr[16 * t], e = ptr[16 * t + 16];
-        for (int32_t x = b; x < e; ++x) {
-            const int32_t q = bucket_of(rel[x]);
-            lo[q] = std::min(lo[q], col[x]);
-            hi[q] = std::max(hi[q], col[x]);
-        }
-        int32_t total = 0;
-        for (int32_t q = 0; q < nb; ++q) {
-            first[q] = total;
-            if (hi[q] >= 0) total += hi[q] - lo[q] + 1;
-        }
-        int32_t nch = (total + 15) / 16;
-        nch += nch & 1;  // even: the kernels consume chunks in pairs
-        const size_t c0 = cols.size(), m0 = map.size();
-        if ((m0 + (size_t)nch * 256) * sizeof(int16_t) > ((size_t)256 << 20)) return BPT_OK;  // too large: no tile path
-        cols.resize(c0 + (size_t)nch * 16, 16 * t);  // padding columns point at a real node and stay masked
-        for (int32_t q = 0; q < nb; ++q)
-            for (int32_t v = lo[q]; hi[q] >= 0 && v <= hi[q]; ++v) cols[c0 + first[q] + (v - lo[q])] = v;
-        map.resize(m0 + (size_t)nch * 256, (int16_t)-1);
-        for (int32_t r = 0; r < 16; ++r) {
-            const int32_t rb = ptr[16 * t + r], re = ptr[16 * t + r + 1];
-            for (int32_t x = rb; x < re; ++x) {
-                const int32_t q = bucket_of(rel[x]);
-                const int32_t slot = first[q] + col[x] - lo[q];
-                const size_t at = m0 + ((size_t)(slot >> 4) * 16 + r) * 16 + (slot & 15);
-                map[at] = (int16_t)cid[rel[x]];
-            }
-        }
-        chunk_ptr.push_back((int32_t)(cols.size() / 16));
-    }
-    out.num_cids = (int32_t)cid_to_id.size();
-    out.num_chunks = chunk_ptr.back();
-    int rc;
-    if ((rc = upload(cid, &out.id_to_cid))) return rc;
-    if ((rc = upload(chunk_ptr, &out.chunk_ptr)) || (rc = upload(cols, &out.cols)) || (rc = upload(map, &out.map)) ||
-        (rc = upload(cid_to_id, &out.cid_to_id)))
-        return rc;
-    out.num_tiles = tiles;
-    return BPT_OK;
-}
-
 void free_key_tiles(KeyTiles& t) {
+    (void)hipFree(t.chunk_ptr);
     (void)hipFree(t.tile_node0);
     (void)hipFree(t.tile_info);
     (void)hipFree(t.cols);
@@ -520,119 +488,6 @@ void free_key_tiles(KeyTiles& t) {
     (void)hipFree(t.multi_tile);
     (void)hipFree(t.multi_ptr);
     t = KeyTiles();
-}
-
-// Key-tile metadata from the token rows of the CSR (span rows are closed form: span
-// (l, m) attends exactly its tokens).  The queries of a tile are bucketed as tokens
-// left of the keys, tokens right of them (for token keys both merge with the keys
-// themselves into one range), then the ancestor levels; a bucket's union is its node
-// range [min, max].  Tile-local relative-position ids: order + k+1 for contextual and
-// self edges, W + l' - 1 for the affiliated edge of the ancestor at level l'.
-int make_key_tiles(int32_t n, int32_t k, int32_t num_levels, int32_t ctx_levels, const std::vector<int32_t>& ptr,
-                   const std::vector<int32_t>& col, const std::vector<int32_t>& rel, KeyTiles& out) {
-    const int32_t W = 2 * (k + 1) + 1, zero = k + 1;
-    if (W + num_levels > 32767) return BPT_OK;
-    std::vector<int32_t> tile_base(ctx_levels + 1, 0);
-    for (int32_t l = 0; l < ctx_levels; ++l) tile_base[l + 1] = tile_base[l] + ((n >> l) + 15) / 16;
-    const int32_t nkt = tile_base[ctx_levels];
-    // pass 1: query ranges per tile; bucket 0 = tokens left of the keys (or all tokens for token keys), 1 = right
-    std::vector<int32_t> lo(2 * (size_t)nkt, INT32_MAX), hi(2 * (size_t)nkt, -1);
-    std::vector<int32_t> key_tile((size_t)ptr[n]);  // tile of every token-row edge's key
-    for (int32_t u = 0; u < n; ++u)
-        for (int32_t x = ptr[u]; x < ptr[u + 1]; ++x) {
-            const int32_t v = col[x], l = rel[x] / W, ord = rel[x] % W - zero;
-            const int32_t kt = tile_base[l] + ((v - (int32_t)level_offset(n, l)) >> 4);
-            key_tile[x] = kt;
-            const size_t b = 2 * (size_t)kt + ((l > 0 && ord < 0) ? 1 : 0);  // ord < 0: key in u's left context
-            lo[b] = std::min(lo[b], u);
-            hi[b] = std::max(hi[b], u);
-        }
-    // layout: chunks per tile, then columns
-    std::vector<int32_t> chunk_ptr(1, 0), first((size_t)2 * nkt + 0), tile_node0(nkt), tile_info(nkt), anc_first(nkt, 0);
-    std::vector<int32_t> cols;
-    size_t total_chunks = 0;
-    for (int32_t l = 0; l < ctx_levels; ++l)
-        for (int32_t kt = tile_base[l]; kt < tile_base[l + 1]; ++kt) {
-            const int32_t m0 = (kt - tile_base[l]) * 16, nkeys = std::min(16, (n >> l) - m0);
-            tile_node0[kt] = (int32_t)level_offset(n, l) + m0;
-            tile_info[kt] = l | (nkeys << 8);
-            int32_t total = 0;
-            for (int32_t b = 0; b < 2; ++b) {
-                first[2 * (size_t)kt + b] = total;
-                if (hi[2 * (size_t)kt + b] >= 0) total += hi[2 * (size_t)kt + b] - lo[2 * (size_t)kt + b] + 1;
-            }
-            anc_first[kt] = total;
-            if (l == 0)  // ancestors of the tile's tokens, level by level
-                for (int32_t la = 1; la < num_levels; ++la) total += ((m0 + nkeys - 1) >> la) - (m0 >> la) + 1;
-            int32_t nch = (total + 15) / 16;
-            nch += nch & 1;
-            total_chunks += nch;
-            if (total_chunks * 512 > ((size_t)512 << 20)) return BPT_OK;  // too large: no tile path
-            const size_t c0 = cols.size();
-            cols.resize(c0 + (size_t)nch * 16, tile_node0[kt]);  // padding columns: a real node, masked
-            size_t at = c0;
-            for (int32_t b = 0; b < 2; ++b)
-                for (int32_t u = lo[2 * (size_t)kt + b]; hi[2 * (size_t)kt + b] >= 0 && u <= hi[2 * (size_t)kt + b]; ++u)
-                    cols[at++] = u;
-            if (l == 0)
-                for (int32_t la = 1; la < num_levels; ++la)
-                    for (int32_t a = m0 >> la; a <= ((m0 + nkeys - 1) >> la); ++a)
-                        cols[at++] = (int32_t)level_offset(n, la) + a;
-            chunk_ptr.push_back((int32_t)(cols.size() / 16));
-        }
-    // pass 2: maps
-    std::vector<int16_t> map(cols.size() * 16, (int16_t)-1);
-    for (int32_t u = 0; u < n; ++u)
-        for (int32_t x = ptr[u]; x < ptr[u + 1]; ++x) {
-            const int32_t kt = key_tile[x], l = rel[x] / W, w = rel[x] % W;
-            const size_t b = 2 * (size_t)kt + ((l > 0 && w - zero < 0) ? 1 : 0);
-            const int32_t slot = first[b] + u - lo[b];
-            const int32_t key = (col[x] - tile_node0[kt]);
-            map[((size_t)chunk_ptr[kt] + (slot >> 4)) * 256 + key * 16 + (slot & 15)] = (int16_t)w;
-        }
-    for (int32_t kt = tile_base[0]; kt < tile_base[1]; ++kt) {  // affiliated edges: ancestor at level la <- token
-        const int32_t m0 = (kt - tile_base[0]) * 16, nkeys = tile_info[kt] >> 8;
-        int32_t slot0 = anc_first[kt];
-        for (int32_t la = 1; la < num_levels; ++la) {
-            for (int32_t key = 0; key < nkeys; ++key) {
-                const int32_t slot = slot0 + ((m0 + key) >> la) - (m0 >> la);
-                map[((size_t)chunk_ptr[kt] + (slot >> 4)) * 256 + key * 16 + (slot & 15)] = (int16_t)(W + la - 1);
-            }
-            slot0 += ((m0 + nkeys - 1) >> la) - (m0 >> la) + 1;
-        }
-    }
-    // tasks
-    std::vector<int32_t> task_tile, task_c0, task_nch, task_part, multi_tile, multi_ptr(1, 0);
-    int32_t parts = 0;
-    const int32_t kKeyTaskChunks = key_task_chunks(n);
-    for (int32_t kt = 0; kt < nkt; ++kt) {
-        const int32_t c0 = chunk_ptr[kt], nch = chunk_ptr[kt + 1] - c0;
-        const int32_t ntask = std::max(1, (nch + kKeyTaskChunks - 1) / kKeyTaskChunks);
-        for (int32_t t = 0; t < ntask; ++t) {
-            task_tile.push_back(kt);
-            task_c0.push_back(c0 + t * kKeyTaskChunks);
-            task_nch.push_back(std::max(0, std::min(kKeyTaskChunks, nch - t * kKeyTaskChunks)));
-            task_part.push_back(ntask > 1 ? parts++ : -1);
-        }
-        if (ntask > 1) {
-            multi_tile.push_back(kt);
-            multi_ptr.push_back(parts);
-        }
-    }
-    out.num_chunks = chunk_ptr.back();
-    out.nb_pad = (W + num_levels - 1 + 15) & ~15;
-    out.first_uncovered = (int32_t)level_offset(n, ctx_levels);
-    out.num_multi = (int32_t)multi_tile.size();
-    out.num_part = parts;
-    int rc;
-    if ((rc = upload(tile_node0, &out.tile_node0)) || (rc = upload(tile_info, &out.tile_info)) ||
-        (rc = upload(cols, &out.cols)) || (rc = upload(map, &out.map)) || (rc = upload(task_tile, &out.task_tile)) ||
-        (rc = upload(task_c0, &out.task_c0)) || (rc = upload(task_nch, &out.task_nch)) ||
-        (rc = upload(task_part, &out.task_part)) || (rc = upload(multi_tile, &out.multi_tile)) ||
-        (rc = upload(multi_ptr, &out.multi_ptr)))
-        return rc;
-    out.num_tasks = (int32_t)task_tile.size();
-    return BPT_OK;
 }
 
 int build(int32_t n, int32_t k, int32_t causal, hipStream_t st, bpt_graph* g) {
@@ -706,10 +561,10 @@ int build(int32_t n, int32_t k, int32_t causal, hipStream_t st, bpt_graph* g) {
     BPT_HIP(hipMalloc((void**)&g->t_rel, sizeof(int32_t) * (size_t)e_all));
     hipLaunchKernelGGL(t_init, dim3(node_blocks), dim3(tb), 0, st, num_nodes, cnt_l.as<int32_t>(), cnt_r.as<int32_t>(),
                        min_l.as<int32_t>(), min_r.as<int32_t>());
-    hipLaunchKernelGGL(t_count, dim3(token_blocks), dim3(tb), 0, st, n, k, g->row_ptr, g->col, g->rel,
-                       cnt_l.as<int32_t>(), cnt_r.as<int32_t>(), min_l.as<int32_t>(), min_r.as<int32_t>());
+    hipLaunchKernelGGL(t_ranges, dim3(token_blocks), dim3(tb), 0, st, n, k, g->causal, cnt_l.as<int32_t>(), cnt_r.as<int32_t>(),
+                       min_l.as<int32_t>(), min_r.as<int32_t>());
     hipLaunchKernelGGL(t_degree, dim3(node_blocks), dim3(tb), 0, st, n, num_nodes, num_levels, cnt_l.as<int32_t>(),
-                       cnt_r.as<int32_t>(), deg.as<int32_t>());
+                       cnt_r.as<int32_t>(), min_l.as<int32_t>(), min_r.as<int32_t>(), deg.as<int32_t>());
     BPT_HIP(hipGetLastError());
     rc = exclusive_scan(deg.as<int32_t>(), g->t_ptr, num_nodes, (int32_t)e_all, block_sums.as<int32_t>(), st);
     if (rc) return rc;
@@ -728,16 +583,10 @@ int build(int32_t n, int32_t k, int32_t causal, hipStream_t st, bpt_graph* g) {
     BPT_HIP(hipStreamSynchronize(st));
     if ((rc = make_schedule(h_ptr, 0, n, g->fwd))) return rc;
     if ((rc = make_schedule(h_tptr, 0, num_nodes, g->tr))) return rc;
-    if (n >= 16 && e_tok < ((int64_t)1 << 27)) {  // dense token tiles for the matrix-core forward
-        std::vector<int32_t> h_col((size_t)e_tok), h_rel((size_t)e_tok);
-        BPT_HIP(hipMemcpyAsync(h_col.data(), g->col, sizeof(int32_t) * h_col.size(), hipMemcpyDeviceToHost, st));
-        BPT_HIP(hipMemcpyAsync(h_rel.data(), g->rel, sizeof(int32_t) * h_rel.size(), hipMemcpyDeviceToHost, st));
-        BPT_HIP(hipStreamSynchronize(st));
-        if ((rc = make_token_tiles(n, k, num_levels, h_ptr, h_col, h_rel, g->tiles))) return rc;
-        if (g->tiles.num_tiles > 0 && (rc = make_schedule(h_ptr, n, n, g->fwd_span))) return rc;
-        if (g->tiles.num_tiles > 0 && (rc = make_key_tiles(n, k, num_levels, g->ctx_levels, h_ptr, h_col, h_rel, g->ktiles)))
-            return rc;
-    }
+    // 6. dense tiles for the matrix-core kernels (GPU, from the CSR on the device)
+    if ((rc = build_tile_metadata(g, cnt_l.as<int32_t>(), min_l.as<int32_t>(), cnt_r.as<int32_t>(), min_r.as<int32_t>(), st)))
+        return rc;
+    if (g->tiles.num_tiles > 0 && (rc = make_schedule(h_ptr, n, n, g->fwd_span))) return rc;
     return BPT_OK;
 }
 

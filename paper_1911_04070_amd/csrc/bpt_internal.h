@@ -59,6 +59,7 @@ struct KeyTiles {
     int32_t num_chunks = 0;         // chunks of all tiles together
     int32_t nb_pad = 0;             // relative-position ids a tile can meet, padded to 16
     int32_t first_uncovered = 0;    // nodes from here on have no in-edges (levels without contextual edges)
+    int32_t* chunk_ptr = nullptr;   // [tiles+1] first chunk of a tile
     int32_t* tile_node0 = nullptr;  // [tiles] first key node
     int32_t* tile_info = nullptr;   // [tiles] level | valid keys << 8
     int32_t* cols = nullptr;        // [chunks][16] query node of a column
@@ -89,6 +90,12 @@ struct bpt_graph {
     bpt::TokenTiles tiles;
     bpt::KeyTiles ktiles;
 };
+
+namespace bpt {
+// bpt_tiles.hip: token tiles and key tiles of a graph whose CSR is on the device
+int build_tile_metadata(bpt_graph* g, const int32_t* cnt_l, const int32_t* min_l, const int32_t* cnt_r,
+                        const int32_t* min_r, hipStream_t st);
+}  // namespace bpt
 
 // Optional per-kernel timing: when enabled, every kernel launch of the library is
 // bracketed by two HIP events on the launch stream (see bpt_profile_enable).
