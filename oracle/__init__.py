@@ -50,6 +50,10 @@ def _load():
         L.bpto_count_edges.argtypes = [i32, i32, i32, p]
         L.bpto_build_graph.restype = i32
         L.bpto_build_graph.argtypes = [i32, i32, i32, p, p, p]
+        L.bpto_count_edges_len.restype = i64
+        L.bpto_count_edges_len.argtypes = [i32, i32, i32, i32, p]
+        L.bpto_build_graph_len.restype = i32
+        L.bpto_build_graph_len.argtypes = [i32, i32, i32, i32, p, p, p]
         L.bpto_transpose.restype = None
         L.bpto_transpose.argtypes = [i32, p, p, p, p, p]
         L.bpto_attn_fwd.restype = i32
@@ -117,6 +121,23 @@ def build_graph(n: int, k: int, causal: bool) -> Graph:
     return Graph(n, k, bool(causal), N, num_levels(n), int(L.bpto_rel_width(k)), row_ptr, col, rel)
 
 
+def build_graph_len(n: int, length: int, k: int, causal: bool) -> Graph:
+    """Graph of a sequence of ``length`` <= n tokens on the node ids of the tree over n:
+    only nodes that hold a token are kept, the other rows are empty."""
+    L = _load()
+    E = L.bpto_count_edges_len(n, length, k, int(causal), None)
+    if E < 0:
+        raise ValueError("n must be a power of two >= 2, k >= 1 and 1 <= length <= n")
+    N = 2 * n - 1
+    row_ptr = np.zeros(N + 1, dtype=np.int32)
+    col = np.zeros(E, dtype=np.int32)
+    rel = np.zeros(E, dtype=np.int32)
+    rc = L.bpto_build_graph_len(n, length, k, int(causal), _ptr(row_ptr), _ptr(col), _ptr(rel))
+    if rc != 0:
+        raise RuntimeError("oracle graph build failed")
+    return Graph(n, k, bool(causal), N, num_levels(n), int(L.bpto_rel_width(k)), row_ptr, col, rel)
+
+
 def transpose(g: Graph):
     """(t_ptr, t_src, t_eid): for each key node its edges in ascending edge index."""
     L = _load()
@@ -170,3 +191,31 @@ def attn_bwd(g: Graph, Q, K, V, Rel, dO, scale: float, threads: int = 0):
                            g.num_levels * g.rel_width, _ptr(Q), _ptr(K), _ptr(V), _ptr(Rel), _ptr(dO),
                            float(scale), _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(dRel), int(threads))
     return dQ, dK, dV, dRel, int(used)
+
+
+def attn_fwd_lengths(n, k, causal, lengths, Q, K, V, Rel, scale: float, threads: int = 0):
+    """Forward of a batch whose b-th sequence has lengths[b] tokens: every batch entry runs
+    on the graph of its own length.  Returns (out, lse, edges) with edges = edge count of
+    the whole batch per head."""
+    out = np.zeros(np.shape(Q), dtype=np.float64)
+    lse = np.zeros(np.shape(Q)[:3], dtype=np.float64)
+    edges = 0
+    for b, length in enumerate(lengths):
+        g = build_graph_len(n, int(length), k, causal)
+        edges += g.num_edges
+        out[b:b + 1], lse[b:b + 1], _ = attn_fwd(g, Q[b:b + 1], K[b:b + 1], V[b:b + 1], Rel, scale, threads)
+    return out, lse, edges
+
+
+def attn_bwd_lengths(n, k, causal, lengths, Q, K, V, Rel, dO, scale: float, threads: int = 0):
+    """Gradient of a batch of sequences of different lengths; dRel is summed over the batch."""
+    dQ = np.zeros(np.shape(Q), dtype=np.float64)
+    dK = np.zeros_like(dQ)
+    dV = np.zeros_like(dQ)
+    dRel = None
+    for b, length in enumerate(lengths):
+        g = build_graph_len(n, int(length), k, causal)
+        q, kk, v, r, _ = attn_bwd(g, Q[b:b + 1], K[b:b + 1], V[b:b + 1], Rel, dO[b:b + 1], scale, threads)
+        dQ[b:b + 1], dK[b:b + 1], dV[b:b + 1] = q, kk, v
+        dRel = r if dRel is None else dRel + r
+    return dQ, dK, dV, dRel

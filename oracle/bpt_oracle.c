@@ -38,6 +38,14 @@
  *     (0,0) is r_self, (j,0) for j>=1 is r_anc(j).
  *   - edges of a row are stored in ascending packed id  level*W + slot.
  *
+ * Sequences of any length (the bpto_*_len functions; the paper states the tree for
+ * n a power of two only, Sec. 3.2.1): a sequence of len tokens, 1 <= len <= n,
+ * keeps the nodes of the tree over n that hold at least one of its tokens --
+ * level l keeps its first ceil(len / 2^l) nodes, the last one possibly cut short --
+ * and Algorithm 1 walks these shorter levels: a run is clipped to the level's
+ * last kept node and the side stops there.  Ids stay those of the tree over n, so
+ * rows of nodes that are not kept are empty; their output is defined as zero.
+ *
  * Node ids: level-major, id(l,m) = off(l) + m with off(l) = 2n - (2n >> l);
  * tokens are 0..n-1 and the root is 2n-2.
  *
@@ -216,6 +224,118 @@ void bpto_transpose(int32_t N, const int32_t *row_ptr, const int32_t *col,
     free(cursor);
 }
 
+/* ---- sequences of len <= n tokens on the tree over n (see the header) ------ */
+
+/* nodes kept on a level */
+static int64_t level_count(int64_t len, int level)
+{
+    return (len + (((int64_t)1 << level) - 1)) >> level;
+}
+
+/* right side of token i when level j holds level_count(len, j) nodes */
+static int right_runs_len(int64_t len, int64_t k, int64_t i, int64_t *first, int64_t *last)
+{
+    int j = 0;
+    int64_t p = i + 1;
+    while (p < level_count(len, j)) {
+        int64_t size = level_count(len, j);
+        int64_t e = p + k - 1;
+        if (e > size - 1) e = size - 1;
+        if ((e & 1) == 0 && e + 1 < size) e += 1;   /* left child whose sibling is kept */
+        first[j] = p;
+        last[j] = e;
+        ++j;
+        if (e + 1 >= size) break;
+        p = (e + 1) >> 1;
+    }
+    return j;
+}
+
+/* Edge count of the graph of a sequence of len tokens; deg[2n-1] optional. */
+int64_t bpto_count_edges_len(int32_t n, int32_t len, int32_t k, int32_t causal, int64_t *deg)
+{
+    if (!is_pow2(n) || k < 1 || len < 1 || len > n) return -1;
+    int32_t levels = bpto_num_levels(n);
+    int64_t total = 0;
+    int64_t f[BPTO_MAX_LEVELS], l[BPTO_MAX_LEVELS];
+    if (deg) memset(deg, 0, sizeof(int64_t) * (size_t)(2 * (int64_t)n - 1));
+    for (int64_t i = 0; i < len; ++i) {
+        int64_t d = 1;
+        int nl = left_runs(n, k, i, f, l);          /* everything left of a token is kept */
+        for (int j = 0; j < nl; ++j) d += f[j] - l[j] + 1;
+        if (!causal) {
+            int nr = right_runs_len(len, k, i, f, l);
+            for (int j = 0; j < nr; ++j) d += l[j] - f[j] + 1;
+        }
+        if (deg) deg[i] = d;
+        total += d;
+    }
+    for (int32_t lev = 1; lev < levels; ++lev) {
+        int64_t off = bpto_level_offset(n, lev);
+        for (int64_t m = 0; m < level_count(len, lev); ++m) {
+            int64_t hi = (m + 1) << lev;
+            if (hi > len) hi = len;
+            if (deg) deg[off + m] = hi - (m << lev);
+            total += hi - (m << lev);
+        }
+    }
+    return total;
+}
+
+/* CSR of that graph over the 2n-1 node ids of the tree over n: row_ptr[2n],
+ * col[E], rel[E]; rows of nodes that are not kept are empty. */
+int32_t bpto_build_graph_len(int32_t n, int32_t len, int32_t k, int32_t causal,
+                             int32_t *row_ptr, int32_t *col, int32_t *rel)
+{
+    int64_t E = bpto_count_edges_len(n, len, k, causal, NULL);
+    if (E < 0 || E > INT32_MAX) return -1;
+    int32_t levels = bpto_num_levels(n);
+    int64_t W = bpto_rel_width(k), zero = k + 1;
+    int64_t lf[BPTO_MAX_LEVELS], ll[BPTO_MAX_LEVELS], rf[BPTO_MAX_LEVELS], rl[BPTO_MAX_LEVELS];
+    int64_t e = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        row_ptr[i] = (int32_t)e;
+        if (i >= len) continue;
+        int nl = left_runs(n, k, i, lf, ll);
+        int nr = causal ? 0 : right_runs_len(len, k, i, rf, rl);
+        int top = nl > nr ? nl : nr;
+        if (top < 1) top = 1;
+        for (int j = 0; j < top; ++j) {
+            int64_t off = bpto_level_offset(n, j);
+            if (j < nl)
+                for (int64_t x = ll[j]; x <= lf[j]; ++x) {
+                    col[e] = (int32_t)(off + x);
+                    rel[e] = (int32_t)(j * W + zero - (lf[j] - x + 1));
+                    ++e;
+                }
+            if (j == 0) {
+                col[e] = (int32_t)i;
+                rel[e] = (int32_t)zero;
+                ++e;
+            }
+            if (j < nr)
+                for (int64_t x = rf[j]; x <= rl[j]; ++x) {
+                    col[e] = (int32_t)(off + x);
+                    rel[e] = (int32_t)(j * W + zero + (x - rf[j] + 1));
+                    ++e;
+                }
+        }
+    }
+    for (int32_t lev = 1; lev < levels; ++lev) {
+        int64_t cnt = (int64_t)n >> lev, off = bpto_level_offset(n, lev);
+        for (int64_t m = 0; m < cnt; ++m) {
+            row_ptr[off + m] = (int32_t)e;
+            for (int64_t t = m << lev; t < ((m + 1) << lev) && t < len; ++t) {
+                col[e] = (int32_t)t;
+                rel[e] = (int32_t)(lev * W + zero);
+                ++e;
+            }
+        }
+    }
+    row_ptr[2 * (int64_t)n - 1] = (int32_t)e;
+    return e == E ? 0 : -1;
+}
+
 /* ---- attention, eq. (6)/(8) -------------------------------------------- */
 
 /* scores of one row into s[], returns lse */
@@ -277,7 +397,7 @@ int32_t bpto_attn_fwd(int32_t N, const int32_t *row_ptr, const int32_t *col, con
                     const float *vv = Vbh + (int64_t)col[b + e] * D;
                     for (int32_t d = 0; d < D; ++d) o[d] += p * (double)vv[d];
                 }
-                lse[(int64_t)bh * N + u] = l;
+                lse[(int64_t)bh * N + u] = deg > 0 ? l : 0.0;   /* a row without edges: zero by definition */
             }
         free(s);
     }

@@ -197,3 +197,88 @@ def test_workload_inputs_are_seeded_and_bf16_exact():
     t = torch.tensor(a["Q"]).to(torch.bfloat16).to(torch.float32).numpy()
     assert np.array_equal(t, a["Q"])
     assert abs(a["Rel"].std() - 0.02) < 0.005 and abs(a["Q"].std() - 1.0) < 0.05
+
+
+# ------------------------------------------------ batches of sequences of different lengths
+def test_lengths_batch_equals_dense_attention_over_kept_nodes():
+    # every batch entry: plain softmax attention (library routine) over the kept nodes of its own
+    # length, forward and gradient; rows of nodes that are not kept give zeros everywhere
+    n, k, D, scale = 32, 2, 8, 0.4
+    lengths = [32, 1, 5, 17, 24]
+    for causal in (False, True):
+        g0 = oracle.build_graph(n, k, causal)
+        Q, K, V, Rel, dO = rand_inputs(g0, len(lengths), 2, D, seed=91 + causal)
+        out, lse, edges = oracle.attn_fwd_lengths(n, k, causal, lengths, Q, K, V, Rel, scale)
+        dQ, dK, dV, dRel = oracle.attn_bwd_lengths(n, k, causal, lengths, Q, K, V, Rel, dO, scale)
+        dRel_ref = np.zeros_like(dRel)
+        assert edges == sum(oracle.build_graph_len(n, x, k, causal).num_edges for x in lengths)
+        for b, length in enumerate(lengths):
+            g = oracle.build_graph_len(n, length, k, causal)
+            rows = np.flatnonzero(np.diff(g.row_ptr) > 0)
+            gone = np.flatnonzero(np.diff(g.row_ptr) == 0)
+            mask, ids = dense_mask_and_ids(g)
+            Qt, Kt, Vt = (torch.tensor(x[b:b + 1], dtype=torch.float64, requires_grad=True) for x in (Q, K, V))
+            Rt = torch.tensor(Rel, dtype=torch.float64, requires_grad=True)
+            R = Rt.reshape(-1, D)[torch.tensor(ids[rows])]
+            bias = scale * torch.einsum("bhud,uvd->bhuv", Qt[:, :, rows], R)
+            bias = bias.masked_fill(~torch.tensor(mask[rows]), float("-inf"))
+            o = torch.nn.functional.scaled_dot_product_attention(Qt[:, :, rows], Kt, Vt, attn_mask=bias, scale=scale)
+            o.backward(torch.tensor(dO[b:b + 1, :, rows], dtype=torch.float64))
+            assert np.abs(out[b:b + 1, :, rows] - o.detach().numpy()).max() < 1e-12
+            for got, leaf in zip((dQ, dK, dV), (Qt, Kt, Vt)):
+                assert np.abs(got[b:b + 1] - leaf.grad.numpy()).max() < 1e-11
+            dRel_ref += Rt.grad.numpy()
+            for t in (out, lse, dQ, dK, dV):
+                assert np.all(t[b][:, gone] == 0)
+        assert np.abs(dRel - dRel_ref).max() < 1e-11
+
+
+def test_power_of_two_length_runs_the_smaller_tree():
+    # a sequence of p = 2^a tokens padded to n gives, on the nodes of the tree over p, exactly
+    # what the graph of the paper over p gives (oracle functions already pinned above)
+    n, p, k, D, scale = 64, 16, 2, 8, 0.3
+    for causal in (False, True):
+        small = oracle.build_graph(p, k, causal)
+        big0 = oracle.build_graph(n, k, causal)
+        Q, K, V, Rel, dO = rand_inputs(big0, 1, 2, D, seed=13)
+        idx = np.concatenate([oracle.level_offset(n, l) + np.arange(p >> l) for l in range(small.num_levels)])
+        sub = lambda x: np.ascontiguousarray(x[:, :, idx])
+        Rs = np.ascontiguousarray(Rel[:small.num_levels])
+        o_s, l_s, _ = oracle.attn_fwd(small, sub(Q), sub(K), sub(V), Rs, scale)
+        g_s = oracle.attn_bwd(small, sub(Q), sub(K), sub(V), Rs, sub(dO), scale)
+        o_b, l_b, _ = oracle.attn_fwd_lengths(n, k, causal, [p], Q, K, V, Rel, scale)
+        # gradient of the nodes of the smaller tree only: the chain above its root gets no dO
+        dO2 = np.zeros_like(dO)
+        dO2[:, :, idx] = dO[:, :, idx]
+        g_b = oracle.attn_bwd_lengths(n, k, causal, [p], Q, K, V, Rel, dO2, scale)
+        assert np.abs(o_b[:, :, idx] - o_s).max() < 1e-13 and np.abs(l_b[:, :, idx] - l_s).max() < 1e-13
+        for a, b in zip(g_b[:3], g_s[:3]):
+            assert np.abs(a[:, :, idx] - b).max() < 1e-12
+        assert np.abs(g_b[3][:small.num_levels] - g_s[3]).max() < 1e-12
+        # each node of the chain above sees the same tokens as the root of the smaller tree
+        root = oracle.level_offset(n, small.num_levels - 1)
+        for level in range(small.num_levels, big0.num_levels):
+            u = oracle.level_offset(n, level)
+            Q2 = Q.copy()
+            Q2[:, :, u] = Q[:, :, root]
+            o2, _, _ = oracle.attn_fwd_lengths(n, k, causal, [p], Q2, K, V, Rel, scale)
+            assert np.abs(o2[:, :, u] - o_b[:, :, root]).max() < 1e-13
+
+
+def test_rows_that_are_not_kept_have_no_influence():
+    n, k, D, scale = 64, 3, 8, 0.25
+    lengths = [37, 64, 2]
+    g0 = oracle.build_graph(n, k, False)
+    Q, K, V, Rel, dO = rand_inputs(g0, 3, 1, D, seed=4)
+    a = oracle.attn_fwd_lengths(n, k, False, lengths, Q, K, V, Rel, scale)[:2] + \
+        oracle.attn_bwd_lengths(n, k, False, lengths, Q, K, V, Rel, dO, scale)
+    rng = np.random.default_rng(1)
+    Q2, K2, V2, dO2 = (x.copy() for x in (Q, K, V, dO))
+    for b, length in enumerate(lengths):
+        gone = np.flatnonzero(np.diff(oracle.build_graph_len(n, length, k, False).row_ptr) == 0)
+        for x in (Q2, K2, V2, dO2):
+            x[b, :, gone] = rng.standard_normal((len(gone), 1, D)).astype(np.float32) * 100
+    b2 = oracle.attn_fwd_lengths(n, k, False, lengths, Q2, K2, V2, Rel, scale)[:2] + \
+        oracle.attn_bwd_lengths(n, k, False, lengths, Q2, K2, V2, Rel, dO2, scale)
+    for x, y in zip(a, b2):
+        assert np.array_equal(x, y)

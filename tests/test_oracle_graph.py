@@ -305,3 +305,143 @@ def test_in_neighbours_are_contiguous_token_ranges(n, k, causal):
             assert np.sum(tok == v) == 1
         else:
             assert len(anc) == 0 and not np.any((tok >= lo) & (tok < hi))
+
+
+# ------------------------------------------- sequences of any length on the tree over n
+# The paper states the tree for n a power of two (Sec. 3.2.1).  The oracle's reading for a
+# sequence of `length` <= n tokens keeps the nodes that hold a token; the checks below pin it
+# to the pinned power-of-two builder (as a sub-graph, and as the smaller tree when the length
+# is itself a power of two), to a declarative search, and to the covering invariant.
+LEN_CASES = [(n, k, c) for n in (2, 4, 8, 16, 32) for k in (1, 2, 3, 5, 40) for c in (False, True)]
+
+
+@pytest.mark.parametrize("n,k,causal", LEN_CASES + [(256, 3, False), (512, 4, True)])
+def test_length_n_is_the_graph_of_the_paper(n, k, causal):
+    a, b = oracle.build_graph_len(n, n, k, causal), oracle.build_graph(n, k, causal)
+    assert np.array_equal(a.row_ptr, b.row_ptr) and np.array_equal(a.col, b.col) and np.array_equal(a.rel, b.rel)
+
+
+def test_length_arguments():
+    for n, length in ((8, 0), (8, 9), (6, 3), (8, -1)):
+        with pytest.raises(ValueError):
+            oracle.build_graph_len(n, length, 2, False)
+
+
+@pytest.mark.parametrize("n,k,causal", LEN_CASES + [(128, 3, False), (256, 2, True), (512, 7, False)])
+def test_length_graph_is_the_sub_graph_of_kept_nodes(n, k, causal):
+    # a node is kept iff its first token exists; an edge iff both ends are kept; packed ids and
+    # the order of a row's edges are those of the full graph
+    full = oracle.build_graph(n, k, causal)
+    keep = np.array([node_span(n, v)[2] for v in range(full.num_nodes)])
+    lengths = range(1, n + 1) if n <= 32 else (1, 2, 3, n // 2 - 1, n // 2, n // 2 + 1, n - 5, n - 1)
+    for length in lengths:
+        g = oracle.build_graph_len(n, length, k, causal)
+        ok = keep < length
+        for u in range(full.num_nodes):
+            c, r = row(full, u)
+            sel = ok[c] & ok[u]
+            gc, gr = row(g, u)
+            assert np.array_equal(gc, c[sel]) and np.array_equal(gr, r[sel]), (n, k, causal, length, u)
+
+
+def tilings_len(length, k, start):
+    """As tilings(), for a sequence whose levels end with a node that may be cut short: the
+    last run is 1..k+1 nodes long, its last node holds a token and reaches the end.  With cut
+    nodes the end of the sequence no longer forces alignment, so the rule for the extra node
+    (Sec. 3.2.2: only when k nodes do not end on a parent boundary) is stated as a constraint."""
+    sols = []
+
+    def rec(level, pos, acc):
+        size = 1 << level
+        if pos % size:
+            return
+        for cnt in range(1, k + 2):
+            last_lo, end = pos + (cnt - 1) * size, pos + cnt * size
+            if last_lo >= length:
+                break
+            if cnt == k + 1 and (pos + k * size) % (2 * size) == 0:
+                continue
+            if end >= length:
+                sols.append(acc + [(level, pos // size, cnt)])
+            elif cnt in (k, k + 1):
+                rec(level + 1, end, acc + [(level, pos // size, cnt)])
+
+    if start < length:
+        rec(0, start, [])
+    else:
+        sols.append([])
+    return sols
+
+
+@pytest.mark.parametrize("n,k", [(n, k) for n in (4, 8, 16, 32) for k in (1, 2, 3, 5, 40)])
+def test_length_right_context_is_the_unique_tiling(n, k):
+    full = oracle.build_graph(n, k, False)
+    for length in range(1, n + 1):
+        g = oracle.build_graph_len(n, length, k, False)
+        for i in range(length):
+            sols = tilings_len(length, k, i + 1)
+            assert len(sols) == 1, (n, k, length, i, sols)
+            expect = {(level, first + t, t + 1) for level, first, cnt in sols[0] for t in range(cnt)}
+            c, r = row(g, i)
+            got, left = set(), []
+            for node, rid in zip(c, r):
+                level, m, lo, hi = node_span(n, int(node))
+                lv, off = unpack(g, rid)
+                assert lv == level
+                if off > 0:
+                    got.add((level, m, off))
+                elif off < 0:
+                    left.append((int(node), int(rid)))
+            assert got == expect, (n, k, length, i)
+            # the left context does not depend on what follows the token
+            fc, fr = row(full, i)
+            assert left == [(int(a), int(b)) for a, b in zip(fc, fr) if unpack(full, b)[1] < 0]
+
+
+@pytest.mark.parametrize("n,k,causal", LEN_CASES + [(64, 3, False), (128, 2, True)])
+def test_length_rows_tile_the_sequence(n, k, causal):
+    lengths = range(1, n + 1) if n <= 32 else (1, 5, 31, 33, 47, 64, 100, n - 1)
+    for length in lengths:
+        if length > n:
+            continue
+        g = oracle.build_graph_len(n, length, k, causal)
+        for i in range(length):
+            c, _ = row(g, i)
+            cover = np.zeros(n, dtype=np.int64)
+            for node in c:
+                _, _, lo, hi = node_span(n, int(node))
+                assert lo < length
+                cover[lo:min(hi, length)] += 1
+            want = np.zeros(n, dtype=np.int64)
+            want[:(i + 1 if causal else length)] = 1
+            assert np.array_equal(cover, want), (n, k, causal, length, i)
+        for u in range(n, g.num_nodes):          # span rows: the tokens they hold, r_anc(level)
+            level, m, lo, hi = node_span(n, u)
+            c, r = row(g, u)
+            assert list(c) == list(range(lo, min(hi, length)))
+            assert all(unpack(g, x) == (level, 0) for x in r)
+        assert g.row_ptr[length] == g.row_ptr[n]                 # tokens beyond the end: empty rows
+
+
+@pytest.mark.parametrize("n,p,k,causal", [(8, 2, 1, False), (16, 4, 2, True), (32, 8, 3, False), (64, 16, 1, True),
+                                           (256, 64, 4, False), (512, 128, 9, True), (64, 32, 40, False)])
+def test_power_of_two_length_is_the_smaller_tree(n, p, k, causal):
+    # a sequence of p = 2^a tokens padded to n: levels 0..a are the tree over p of the paper;
+    # each higher level keeps one node, which holds all p tokens
+    g = oracle.build_graph_len(n, p, k, causal)
+    small = oracle.build_graph(p, k, causal)
+    to_big = np.zeros(small.num_nodes, dtype=np.int64)
+    for v in range(small.num_nodes):
+        level, m, _, _ = node_span(p, v)
+        to_big[v] = oracle.level_offset(n, level) + m
+    for v in range(small.num_nodes):
+        c, r = row(small, v)
+        gc, gr = row(g, int(to_big[v]))
+        assert np.array_equal(gc, to_big[c]) and np.array_equal(gr, r), (v,)
+    top = small.num_levels
+    for level in range(top, g.num_levels):
+        c, r = row(g, oracle.level_offset(n, level))
+        assert list(c) == list(range(p)) and all(unpack(g, x) == (level, 0) for x in r)
+    used = set(int(x) for x in to_big) | {oracle.level_offset(n, l) for l in range(top, g.num_levels)}
+    deg = np.diff(g.row_ptr)
+    assert all(deg[u] == 0 for u in range(g.num_nodes) if u not in used)
