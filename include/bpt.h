@@ -32,6 +32,17 @@
  *     with D contiguous and element strides stride_b, stride_h, stride_n
  *     (the same for all of them); lse is contiguous [B][H][N] fp32.
  *   - Outputs are fully overwritten, never accumulated into.
+ *
+ * Sequences shorter than n (batches of sequences of different lengths).  The paper
+ * states the tree for n a power of two (Sec. 3.2.1).  A batch entry b with
+ * len = seq_len[b] < n tokens lives on the same node ids and keeps the nodes that hold
+ * at least one of its tokens: node (l, m) is kept iff m * 2^l < len, so level l keeps
+ * its first ceil(len / 2^l) nodes, the last one possibly cut short.  An edge of the
+ * graph counts iff both of its nodes are kept; this is what Algorithm 1 gives when its
+ * runs are clipped to the kept nodes of each level.  Rows of nodes that are not kept
+ * produce zeros in every output (out, lse, dQ, dK, dV) and add nothing to d_rel; their
+ * input rows are never used but must hold finite values.  Values of seq_len outside
+ * [0, n] are clamped.
  */
 #ifndef BPT_H_
 #define BPT_H_
@@ -61,6 +72,8 @@ typedef struct {
     int32_t dtype;       /* bpt_dtype_t of Q, K, V, rel, out, dout */
     int64_t stride_b, stride_h, stride_n; /* in elements; stride_n >= D, multiples of 8 */
     float scale;         /* softmax scale; <= 0 selects 1/sqrt(D) (Sec. 3.1 eq. (6)) */
+    const int32_t* seq_len; /* device pointer to B token counts, or NULL: every sequence has n
+                              tokens.  See "Sequences shorter than n" above. */
 } bpt_shape_t;
 
 /* Sec. 3.2 + Algorithm 1.  Builds, on the current device, the graph of a

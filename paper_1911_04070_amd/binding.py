@@ -30,7 +30,7 @@ EXPORTS = [
 class BptShape(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("D", ctypes.c_int32), ("dtype", ctypes.c_int32),
                 ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64), ("stride_n", ctypes.c_int64),
-                ("scale", ctypes.c_float)]
+                ("scale", ctypes.c_float), ("seq_len", ctypes.c_void_p)]
 
 
 class BptError(RuntimeError):
@@ -167,7 +167,7 @@ def bpt_build_graph(n: int, k: int, causal: bool) -> Graph:
     return Graph(n, k, causal)
 
 
-def _shape_of(g: Graph, x: torch.Tensor, scale: Optional[float]) -> BptShape:
+def _shape_of(g: Graph, x: torch.Tensor, scale: Optional[float], seq_len: Optional[torch.Tensor] = None) -> BptShape:
     if x.dim() != 4 or x.shape[2] != g.num_nodes:
         raise ValueError("expected a [B,H,N=%d,D] tensor, got %s" % (g.num_nodes, tuple(x.shape)))
     if x.stride(3) != 1:
@@ -179,7 +179,13 @@ def _shape_of(g: Graph, x: torch.Tensor, scale: Optional[float]) -> BptShape:
     else:
         raise ValueError("dtype must be float32 or bfloat16")
     B, H, _, D = x.shape
-    return BptShape(B, H, D, dt, x.stride(0), x.stride(1), x.stride(2), float(scale) if scale else 0.0)
+    lens = None
+    if seq_len is not None:
+        if seq_len.dtype != torch.int32 or tuple(seq_len.shape) != (B,) or not seq_len.is_contiguous() or \
+                seq_len.device != x.device:
+            raise ValueError("seq_len must be a contiguous int32 tensor of B entries on the tensors' device")
+        lens = seq_len.data_ptr()
+    return BptShape(B, H, D, dt, x.stride(0), x.stride(1), x.stride(2), float(scale) if scale else 0.0, lens)
 
 
 def _same_layout(ref: torch.Tensor, *others: torch.Tensor) -> None:
@@ -197,10 +203,12 @@ def _workspace(nbytes: int, device) -> Tuple[Optional[torch.Tensor], int]:
 
 def bpt_attn_fwd(g: Graph, Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, rel: torch.Tensor,
                  scale: Optional[float] = None, out: Optional[torch.Tensor] = None,
-                 lse: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None):
-    """out, lse = graph attention of eq. (8).  Q,K,V: [B,H,N,D] cuda tensors; rel: [levels,W,D]."""
+                 lse: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                 seq_len: Optional[torch.Tensor] = None):
+    """out, lse = graph attention of eq. (8).  Q,K,V: [B,H,N,D] cuda tensors; rel: [levels,W,D];
+    seq_len: optional int32 [B] token counts of sequences shorter than n."""
     L = load_library()
-    shp = _shape_of(g, Q, scale)
+    shp = _shape_of(g, Q, scale, seq_len)
     _same_layout(Q, K, V)
     if K.dtype != Q.dtype or V.dtype != Q.dtype or rel.dtype != Q.dtype:
         raise ValueError("Q, K, V and rel must share a dtype")
@@ -222,9 +230,9 @@ def bpt_attn_fwd(g: Graph, Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, re
     return out, lse
 
 
-def _bwd_prepare(g, Q, K, V, rel, lse, dout, scale, grads, workspace):
+def _bwd_prepare(g, Q, K, V, rel, lse, dout, scale, grads, workspace, seq_len=None):
     L = load_library()
-    shp = _shape_of(g, Q, scale)
+    shp = _shape_of(g, Q, scale, seq_len)
     _same_layout(Q, K, V, dout)
     if lse.dtype != torch.float32 or tuple(lse.shape) != tuple(Q.shape[:3]) or not lse.is_contiguous():
         raise ValueError("lse must be contiguous fp32 [B,H,N]")
@@ -243,9 +251,11 @@ def _bwd_prepare(g, Q, K, V, rel, lse, dout, scale, grads, workspace):
 
 
 def bpt_attn_bwd(g: Graph, Q, K, V, rel, lse, dout, scale: Optional[float] = None,
-                 grads: Optional[Tuple[torch.Tensor, ...]] = None, workspace: Optional[torch.Tensor] = None):
+                 grads: Optional[Tuple[torch.Tensor, ...]] = None, workspace: Optional[torch.Tensor] = None,
+                 seq_len: Optional[torch.Tensor] = None):
     """dQ, dK, dV, d_rel (all fp32) = gradient of eq. (8) given dout and the forward's lse."""
-    L, shp, (dQ, dK, dV, d_rel), ws, ws_bytes = _bwd_prepare(g, Q, K, V, rel, lse, dout, scale, grads, workspace)
+    L, shp, (dQ, dK, dV, d_rel), ws, ws_bytes = _bwd_prepare(g, Q, K, V, rel, lse, dout, scale, grads, workspace,
+                                                             seq_len)
     _check(L.bpt_attn_bwd(g.handle, ctypes.byref(shp), Q.data_ptr(), K.data_ptr(), V.data_ptr(), rel.data_ptr(),
                           lse.data_ptr(), dout.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(),
                           d_rel.data_ptr(), ws.data_ptr(), ws_bytes, _stream_ptr()), "bpt_attn_bwd")
@@ -253,10 +263,10 @@ def bpt_attn_bwd(g: Graph, Q, K, V, rel, lse, dout, scale: Optional[float] = Non
 
 
 def bpt_attn_bwd_query_side(g: Graph, Q, K, V, rel, lse, dout, dQ, d_rel, workspace,
-                            scale: Optional[float] = None):
+                            scale: Optional[float] = None, seq_len: Optional[torch.Tensor] = None):
     """First stage of the backward: dQ, d_rel, and delta into the workspace."""
     L = load_library()
-    shp = _shape_of(g, Q, scale)
+    shp = _shape_of(g, Q, scale, seq_len)
     _check(L.bpt_attn_bwd_query_side(g.handle, ctypes.byref(shp), Q.data_ptr(), K.data_ptr(), V.data_ptr(),
                                      rel.data_ptr(), lse.data_ptr(), dout.data_ptr(), dQ.data_ptr(),
                                      d_rel.data_ptr(), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
@@ -264,10 +274,11 @@ def bpt_attn_bwd_query_side(g: Graph, Q, K, V, rel, lse, dout, dQ, d_rel, worksp
     return dQ, d_rel
 
 
-def bpt_attn_bwd_key_side(g: Graph, Q, K, V, rel, lse, dout, dK, dV, workspace, scale: Optional[float] = None):
+def bpt_attn_bwd_key_side(g: Graph, Q, K, V, rel, lse, dout, dK, dV, workspace, scale: Optional[float] = None,
+                          seq_len: Optional[torch.Tensor] = None):
     """Second stage of the backward: dK, dV (reads delta from the workspace)."""
     L = load_library()
-    shp = _shape_of(g, Q, scale)
+    shp = _shape_of(g, Q, scale, seq_len)
     _check(L.bpt_attn_bwd_key_side(g.handle, ctypes.byref(shp), Q.data_ptr(), K.data_ptr(), V.data_ptr(),
                                    rel.data_ptr(), lse.data_ptr(), dout.data_ptr(), dK.data_ptr(), dV.data_ptr(),
                                    workspace.data_ptr(),

@@ -42,7 +42,23 @@ struct AttnArgs {
     int32_t drel_rows;      // rows of d_rel that token rows can touch (levels with contextual edges)
     int32_t drel_block;     // token rows per block of rel_grad_kernel
     int32_t rel_rows;       // rows of the whole table
+    const int32_t* seq_len; // [B] tokens of every sequence, or null: all have n_tokens
+    int32_t lg;             // log2(n_tokens)
 };
+
+// ---- sequences shorter than n ------------------------------------------------------
+// A batch entry with len < n tokens keeps the nodes whose first token exists; an edge counts
+// iff both of its nodes are kept.  Rows of nodes that are not kept produce zeros.
+__device__ __forceinline__ int seq_length(const int32_t* seq_len, int b, int n) {
+    return seq_len ? min(max(seq_len[b], 0), n) : n;
+}
+// first token of a node of the tree over n = 2^lg tokens (ids are level-major)
+__device__ __forceinline__ int node_first_token(int id, int lg) {
+    const int x = (2 << lg) - id;                  // (n >> l) < x <= (2n >> l) on level l
+    const int level = lg - (31 - __clz(x - 1));
+    return (((2 << lg) >> level) - x) << level;
+}
+constexpr float kLseGone = 1.0e30f;   // stands for lse * log2(e) of a row that is not kept: exp2(s - kLseGone) = 0
 
 // ---- lane helpers ---------------------------------------------------------------
 template <int CTRL>

@@ -30,16 +30,18 @@ namespace {
 template <typename T, bool REL_LDS, bool SPAN>
 __device__ __forceinline__ void fwd_segment(const AttnArgs& a, const T* rel_s, rsrc_t rK, rsrc_t rV, rsrc_t rIa,
                                             rsrc_t rIb, int bh, int64_t base, int u, int e0, int e1, int part,
-                                            int lane) {
+                                            int lane, int len) {
     const int slot = lane >> 3, sub = lane & 7;
     const int lane_off = sub * 8 * (int)sizeof(T);
     const T* relg = static_cast<const T*>(a.rel) + sub * 8;
+    const bool row_kept = node_first_token(u, a.lg) < len;
 
     // indices two iterations ahead, rows one iteration ahead.  Lanes past the end of
     // the segment read the next rows' indices (or 0 past the array): valid nodes,
     // and their contribution is masked.
     int eo = (e0 + slot) * 4;
     const int c0 = buf_i32(rIa, eo);
+    int cnow = c0;   // key node of the rows in work
     int c1 = buf_i32(rIa, eo + 32);
     int r0 = 0, r1 = 0;
     if (!SPAN) {
@@ -68,7 +70,8 @@ __device__ __forceinline__ void fwd_segment(const AttnArgs& a, const T* rel_s, r
         vn = gather_row<T>(rV, c1, a.row_bytes, lane_off);
         eo += 32;
 
-        const bool valid = eb + slot < e1;
+        const bool valid = eb + slot < e1 && row_kept && node_first_token(cnow, a.lg) < len;
+        cnow = c1;
         float vv[8], d = 0.f;
         if (!SPAN) {
             const int rid = valid ? r0 : 0;  // a masked lane may hold an id of some other row
@@ -111,7 +114,7 @@ __device__ __forceinline__ void fwd_segment(const AttnArgs& a, const T* rel_s, r
     const int col = sub * 8 + slot_elem(lane);
     if (part < 0) {
         store1(static_cast<T*>(a.out) + base + (int64_t)u * a.sn + col, l > 0.f ? mine / l : 0.f);
-        if (lane == 0) a.lse_w[(int64_t)bh * a.N + u] = (mall + fast_log2(l)) * kLn2;
+        if (lane == 0) a.lse_w[(int64_t)bh * a.N + u] = l > 0.f ? (mall + fast_log2(l)) * kLn2 : 0.f;
     } else {
         float* dst = a.part + ((int64_t)bh * a.num_part + part) * kPartStride;
         dst[col] = mine;
@@ -129,7 +132,7 @@ __device__ __forceinline__ void fwd_segment(const AttnArgs& a, const T* rel_s, r
 // and one wavefront per row would spend its time in row set-up.
 template <typename T>
 __device__ __forceinline__ void fwd_span8(const AttnArgs& a, rsrc_t rK, rsrc_t rV, int bh, int64_t base, int u0, int e0,
-                                          int deg, int lane) {
+                                          int deg, int lane, int len) {
     const int slot = lane >> 3, sub = lane & 7;
     const int lane_off = sub * 8 * (int)sizeof(T);
     const int u = u0 + slot;
@@ -146,10 +149,11 @@ __device__ __forceinline__ void fwd_span8(const AttnArgs& a, rsrc_t rK, rsrc_t r
         const int nxt = tok0 + min(i + 1, deg - 1);
         kn = gather_row<T>(rK, nxt, a.row_bytes, lane_off);
         vn = gather_row<T>(rV, nxt, a.row_bytes, lane_off);
-        const float sc = sum8(dot8(q, kc, 0.f)) * qscale + shift;
+        const bool valid = tok0 + i < len;
+        const float sc = valid ? sum8(dot8(q, kc, 0.f)) * qscale + shift : kNegBig;
         const bool up = sc > m;
         const float e = fast_exp2(up ? m - sc : sc - m);
-        const float corr = up ? e : 1.f, p = up ? 1.f : e;
+        const float corr = up ? e : 1.f, p = valid ? (up ? 1.f : e) : 0.f;
         m = up ? sc : m;
         float vv[8];
         unpack(vc, vv);
@@ -166,11 +170,11 @@ __device__ __forceinline__ void fwd_span8(const AttnArgs& a, rsrc_t rK, rsrc_t r
         step(i, k0, v0, k1, v1);
         step(i + 1, k1, v1, k0, v0);
     }
-    const float inv = 1.f / l;
+    const float inv = l > 0.f ? 1.f / l : 0.f;   // l == 0: a span past the end of a shorter sequence
 #pragma unroll
     for (int x = 0; x < 8; ++x) acc[x] *= inv;
     store8(static_cast<T*>(a.out) + base + (int64_t)u * a.sn + sub * 8, acc);
-    if (sub == 0) a.lse_w[(int64_t)bh * a.N + u] = (m + fast_log2(l)) * kLn2;
+    if (sub == 0) a.lse_w[(int64_t)bh * a.N + u] = l > 0.f ? (m + fast_log2(l)) * kLn2 : 0.f;
 }
 
 template <typename T, bool REL_LDS>
@@ -190,6 +194,7 @@ __global__ void __launch_bounds__(kThreads) fwd_kernel(const AttnArgs a) {
         const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
         const rsrc_t rK = make_rsrc(static_cast<const T*>(a.K) + base, a.slab_bytes);
         const rsrc_t rV = make_rsrc(static_cast<const T*>(a.V) + base, a.slab_bytes);
+        const int len = seq_length(a.seq_len, bh / a.H, a.n_tokens);
         const int s1 = a.tile_ptr[tile + 1];
         for (int s = a.tile_ptr[tile] + wave; s < s1; s += nwaves) {
             const int u = a.seg_row[s];
@@ -198,11 +203,11 @@ __global__ void __launch_bounds__(kThreads) fwd_kernel(const AttnArgs a) {
             const int part = a.seg_part[s];
             if (e1 <= e0) continue;  // no row of this adjacency is empty
             if (part == kPartSpan8)
-                fwd_span8<T>(a, rK, rV, bh, base, u, e0, a.ptr[u + 1] - e0, lane);
+                fwd_span8<T>(a, rK, rV, bh, base, u, e0, a.ptr[u + 1] - e0, lane, len);
             else if (u >= a.n_tokens)
-                fwd_segment<T, REL_LDS, true>(a, rel_s, rK, rV, rIa, rIb, bh, base, u, e0, e1, part, lane);
+                fwd_segment<T, REL_LDS, true>(a, rel_s, rK, rV, rIa, rIb, bh, base, u, e0, e1, part, lane, len);
             else
-                fwd_segment<T, REL_LDS, false>(a, rel_s, rK, rV, rIa, rIb, bh, base, u, e0, e1, part, lane);
+                fwd_segment<T, REL_LDS, false>(a, rel_s, rK, rV, rIa, rIb, bh, base, u, e0, e1, part, lane, len);
         }
     }
 }
@@ -228,7 +233,7 @@ __global__ void __launch_bounds__(256) fwd_merge_kernel(const AttnArgs a, const 
     }
     const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
     store1(static_cast<T*>(a.out) + base + (int64_t)u * a.sn + lane, l > 0.f ? acc / l : 0.f);
-    if (lane == 0) a.lse_w[(int64_t)bh * a.N + u] = (m + fast_log2(l)) * kLn2;
+    if (lane == 0) a.lse_w[(int64_t)bh * a.N + u] = l > 0.f ? (m + fast_log2(l)) * kLn2 : 0.f;
 }
 
 // ---- backward, query side: delta and dQ ------------------------------------------------
@@ -240,13 +245,15 @@ __global__ void __launch_bounds__(256) fwd_merge_kernel(const AttnArgs a, const 
 template <typename T, bool REL_LDS, bool SPAN>
 __device__ __forceinline__ void bwd_q_segment(const AttnArgs& a, const T* rel_s, rsrc_t rK, rsrc_t rV, rsrc_t rIa,
                                               rsrc_t rIb, int bh, int64_t base, int u, int e0, int e1, int part,
-                                              int lane) {
+                                              int lane, int len) {
     const int slot = lane >> 3, sub = lane & 7;
     const int lane_off = sub * 8 * (int)sizeof(T);
     const T* relg = static_cast<const T*>(a.rel) + sub * 8;
+    const bool row_kept = node_first_token(u, a.lg) < len;
 
     int eo = (e0 + slot) * 4;
     const int c0 = buf_i32(rIa, eo);
+    int cnow = c0;   // key node of the rows in work
     int c1 = buf_i32(rIa, eo + 32);
     int r0 = 0, r1 = 0;
     if (!SPAN) {
@@ -281,12 +288,14 @@ __device__ __forceinline__ void bwd_q_segment(const AttnArgs& a, const T* rel_s,
         kn = gather_row<T>(rK, c1, a.row_bytes, lane_off);
         vn = gather_row<T>(rV, c1, a.row_bytes, lane_off);
 
-        const bool valid = eb + slot < e1;
+        const bool inside = eb + slot < e1;
+        const bool valid = inside && row_kept && node_first_token(cnow, a.lg) < len;
+        cnow = c1;
         float kk[8];
         unpack(kc, kk);
         if (!SPAN) {
             float r[8];
-            const int rid = valid ? r0 : 0;  // a masked lane may hold an id of some other row
+            const int rid = inside ? r0 : 0;  // a lane past the end may hold an id of some other row
             if (REL_LDS)
                 load8(rel_s + rid * kD + sub * 8, r);
             else
@@ -308,7 +317,7 @@ __device__ __forceinline__ void bwd_q_segment(const AttnArgs& a, const T* rel_s,
             Bv[i] = fmaf(p, kk[i], Bv[i]);
         }
         // what d_rel needs of this edge (dS_e = w_e - delta_u p_e once delta_u is known)
-        if (!SPAN && valid && sub == 0) a.wp[(int64_t)bh * a.e_tok + (eo >> 2)] = make_float2(wgt, p);
+        if (!SPAN && inside && sub == 0) a.wp[(int64_t)bh * a.e_tok + (eo >> 2)] = make_float2(wgt, p);
         eo += 32;
         c1 = c2;
         r0 = r1;
@@ -326,7 +335,7 @@ __device__ __forceinline__ void bwd_q_segment(const AttnArgs& a, const T* rel_s,
 #pragma unroll
         for (int i = 0; i < 8; ++i) A[i] -= dl * Bv[i];
         a.dQ[base + (int64_t)u * a.sn + col] = a.scale * reduce_slots8(A, lane);
-        if (lane == 0) a.stat[(int64_t)bh * a.N + u] = make_float2(lse2, dl);
+        if (lane == 0) a.stat[(int64_t)bh * a.N + u] = make_float2(row_kept ? lse2 : kLseGone, dl);
     } else {
         float* dst = a.part + ((int64_t)bh * a.num_part + part) * kQPartStride;
         dst[col] = reduce_slots8(A, lane);
@@ -338,7 +347,7 @@ __device__ __forceinline__ void bwd_q_segment(const AttnArgs& a, const T* rel_s,
 // Query side of eight consecutive short span rows, one row per 8-lane group (see fwd_span8).
 template <typename T>
 __device__ __forceinline__ void bwd_q_span8(const AttnArgs& a, rsrc_t rK, rsrc_t rV, int bh, int64_t base, int u0,
-                                            int e0, int deg, int lane) {
+                                            int e0, int deg, int lane, int len) {
     const int slot = lane >> 3, sub = lane & 7;
     const int lane_off = sub * 8 * (int)sizeof(T);
     const int u = u0 + slot;
@@ -370,7 +379,7 @@ __device__ __forceinline__ void bwd_q_span8(const AttnArgs& a, rsrc_t rK, rsrc_t
         unpack(kc, kk);
 #pragma unroll
         for (int x = 0; x < 8; ++x) d += qs[x] * kk[x];
-        const float p = fast_exp2(sum8(d) + shift - lse2);
+        const float p = tok0 + i < len ? fast_exp2(sum8(d) + shift - lse2) : 0.f;
         const float wgt = p * sum8(dot8(g, vc, 0.f));
         dl += wgt;
 #pragma unroll
@@ -387,7 +396,7 @@ __device__ __forceinline__ void bwd_q_span8(const AttnArgs& a, rsrc_t rK, rsrc_t
 #pragma unroll
     for (int x = 0; x < 8; ++x) A[x] = a.scale * (A[x] - dl * Bv[x]);
     store8(a.dQ + base + (int64_t)u * a.sn + sub * 8, A);
-    if (sub == 0) a.stat[(int64_t)bh * a.N + u] = make_float2(lse2, dl);
+    if (sub == 0) a.stat[(int64_t)bh * a.N + u] = make_float2(tok0 < len ? lse2 : kLseGone, dl);
 }
 
 template <typename T, bool REL_LDS>
@@ -407,6 +416,7 @@ __global__ void __launch_bounds__(kThreads) bwd_q_kernel(const AttnArgs a) {
         const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
         const rsrc_t rK = make_rsrc(static_cast<const T*>(a.K) + base, a.slab_bytes);
         const rsrc_t rV = make_rsrc(static_cast<const T*>(a.V) + base, a.slab_bytes);
+        const int len = seq_length(a.seq_len, bh / a.H, a.n_tokens);
         const int s1 = a.tile_ptr[tile + 1];
         for (int s = a.tile_ptr[tile] + wave; s < s1; s += nwaves) {
             const int u = a.seg_row[s];
@@ -415,11 +425,11 @@ __global__ void __launch_bounds__(kThreads) bwd_q_kernel(const AttnArgs a) {
             const int part = a.seg_part[s];
             if (e1 <= e0) continue;
             if (part == kPartSpan8)
-                bwd_q_span8<T>(a, rK, rV, bh, base, u, e0, a.ptr[u + 1] - e0, lane);
+                bwd_q_span8<T>(a, rK, rV, bh, base, u, e0, a.ptr[u + 1] - e0, lane, len);
             else if (u >= a.n_tokens)
-                bwd_q_segment<T, REL_LDS, true>(a, rel_s, rK, rV, rIa, rIb, bh, base, u, e0, e1, part, lane);
+                bwd_q_segment<T, REL_LDS, true>(a, rel_s, rK, rV, rIa, rIb, bh, base, u, e0, e1, part, lane, len);
             else
-                bwd_q_segment<T, REL_LDS, false>(a, rel_s, rK, rV, rIa, rIb, bh, base, u, e0, e1, part, lane);
+                bwd_q_segment<T, REL_LDS, false>(a, rel_s, rK, rV, rIa, rIb, bh, base, u, e0, e1, part, lane, len);
         }
     }
 }
@@ -441,7 +451,8 @@ __global__ void __launch_bounds__(256) bwd_q_merge_kernel(const AttnArgs a, cons
     }
     const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
     a.dQ[base + (int64_t)u * a.sn + lane] = a.scale * (sa - dl * sb);
-    if (lane == 0) a.stat[(int64_t)bh * a.N + u] = make_float2(a.lse_r[(int64_t)bh * a.N + u] * kLog2e, dl);
+    const bool kept = node_first_token(u, a.lg) < seq_length(a.seq_len, bh / a.H, a.n_tokens);
+    if (lane == 0) a.stat[(int64_t)bh * a.N + u] = make_float2(kept ? a.lse_r[(int64_t)bh * a.N + u] * kLog2e : kLseGone, dl);
 }
 
 // ---- backward, key side: dK, dV over the transposed adjacency -------------------------
@@ -451,7 +462,7 @@ __global__ void __launch_bounds__(256) bwd_q_merge_kernel(const AttnArgs a, cons
 template <typename T, bool REL_LDS>
 __device__ __forceinline__ void bwd_kv_segment(const AttnArgs& a, const T* rel_s, rsrc_t rQ, rsrc_t rG, rsrc_t rS,
                                                rsrc_t rIa, rsrc_t rIb, int bh, int64_t base, int v, int e0, int e1,
-                                               int part, int lane) {
+                                               int part, int lane, int len) {
     const int slot = lane >> 3, sub = lane & 7;
     const int lane_off = sub * 8 * (int)sizeof(T);
     const T* relg = static_cast<const T*>(a.rel) + sub * 8;
@@ -461,7 +472,8 @@ __device__ __forceinline__ void bwd_kv_segment(const AttnArgs& a, const T* rel_s
 #pragma unroll
     for (int i = 0; i < 8; ++i) dk[i] = dv[i] = 0.f;
 
-    if (e1 > e0) {
+    // queries that are not kept carry kLseGone in `stat`; a key that is not kept has no edge at all
+    if (e1 > e0 && node_first_token(v, a.lg) < len) {
         int eo = (e0 + slot) * 4;
         const int u0 = buf_i32(rIa, eo);
         int u1 = buf_i32(rIa, eo + 32);
@@ -542,7 +554,8 @@ __global__ void __launch_bounds__(kThreads) bwd_kv_kernel(const AttnArgs a) {
             const int v = a.seg_row[s];
             const int e0 = a.seg_begin[s];
             const int e1 = min(e0 + kSeg, a.ptr[v + 1]);
-            bwd_kv_segment<T, REL_LDS>(a, rel_s, rQ, rG, rS, rIa, rIb, bh, base, v, e0, e1, a.seg_part[s], lane);
+            bwd_kv_segment<T, REL_LDS>(a, rel_s, rQ, rG, rS, rIa, rIb, bh, base, v, e0, e1, a.seg_part[s], lane,
+                                       seq_length(a.seq_len, bh / a.H, a.n_tokens));
         }
     }
 }

@@ -32,6 +32,8 @@ struct KeyArgs {
     const int32_t *tile_node0, *tile_info, *cols, *task_tile, *task_c0, *task_nch, *task_part;
     const int16_t* map;
     int32_t num_tasks, num_part, num_chunks, nb_pad, W, zero;
+    const int32_t* seq_len;   // [B] tokens of every sequence, or null
+    int32_t n;
 };
 
 template <int NBC>
@@ -61,6 +63,11 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyA
         const int kt = a.task_tile[task], c0 = a.task_c0[task], nch = a.task_nch[task], part = a.task_part[task];
         const int node0 = a.tile_node0[kt], info = a.tile_info[kt];
         const int level = info & 255, nkeys = info >> 8;
+        // a shorter sequence keeps the first ceil(len / 2^level) nodes of the level; queries that are
+        // not kept carry kLseGone in `stat`
+        const int len = seq_length(a.seq_len, bh / a.H, a.n);
+        const int kept_keys = ((len + (1 << level) - 1) >> level) - (node0 - (2 * a.n - ((2 * a.n) >> level)));
+        const bool key_kept = j < kept_keys;
         const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
         const rsrc_t rQ = make_rsrc(a.Q + base, a.slab_bytes), rG = make_rsrc(a.dout + base, a.slab_bytes);
         const rsrc_t rS = make_rsrc(a.stat + (int64_t)bh * a.N, (uint32_t)a.N * 8u);
@@ -198,7 +205,7 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyA
             for (int ci = 0; ci < 2; ++ci)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const float p = bid[ci][r] >= 0 ? fast_exp2((s4[ci][r] + bv[ci][r]) * qscale - st[ci][r].x) : 0.f;
+                    const float p = bid[ci][r] >= 0 && key_kept ? fast_exp2((s4[ci][r] + bv[ci][r]) * qscale - st[ci][r].x) : 0.f;
                     pp[ci][r] = p;
                     ds[ci][r] = p * (d4[ci][r] - st[ci][r].y);
                 }

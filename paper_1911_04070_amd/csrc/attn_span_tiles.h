@@ -34,6 +34,7 @@ struct SpanArgs {
     int64_t sb, sh, sn;
     int32_t BH, H, N, n, L, W, zero;
     float scale;
+    const int32_t* seq_len;   // [B] tokens of every sequence, or null
 };
 __device__ __forceinline__ int span_level_offset(int n, int level) { return 2 * n - ((2 * n) >> level); }
 // query slot -> (level, index inside the block at that level); group is wave-uniform
@@ -85,6 +86,7 @@ __global__ void __launch_bounds__(kTileThreads) fwd_span_tile_kernel(const SpanA
     const float qscale = a.scale * kLog2e;
     const int ngroups = a.L > kSpanInLevels ? 3 : 2;
     const int nanc = a.L - kSpanInLevels;
+    const int len = seq_length(a.seq_len, bh / a.H, a.n);   // tokens from `len` on do not exist
 
     // the block's K rows as A operands (token j of chunk c, features 16g..16g+15); V rows into LDS
     bf16x8_t ka[2][2];
@@ -120,7 +122,7 @@ __global__ void __launch_bounds__(kTileThreads) fwd_span_tile_kernel(const SpanA
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int tt = 16 * c + 4 * g + r;   // token of the block
-                const bool member = valid && (grp == 2 || (tt >> level) == loc);
+                const bool member = valid && (grp == 2 || (tt >> level) == loc) && t0 + tt < len;
                 p[c][r] = member ? s4[r] * qscale + shift : kNegBig;
                 m = fmaxf(m, p[c][r]);
             }
@@ -151,14 +153,15 @@ __global__ void __launch_bounds__(kTileThreads) fwd_span_tile_kernel(const SpanA
         }
         // C[m = query][n = feature]: this lane holds queries 4g..4g+3, feature 16f + j
         if (grp < 2) {
-            if (g == 0 && valid) a.lse[(int64_t)bh * a.N + node] = (m + fast_log2(l)) * kLn2;
+            // l == 0: a span past the end of a shorter sequence, its row is zero
+            if (g == 0 && valid) a.lse[(int64_t)bh * a.N + node] = l > 0.f ? (m + fast_log2(l)) * kLn2 : 0.f;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int slot = 4 * g + r;
                 const float lq = __shfl(l, slot);
                 if (grp == 1 && slot == 15) continue;
                 bf16_t* orow = a.out + base + (int64_t)span_slot_node(grp, slot, a.L, a.n, t0) * a.sn + j;
-                const float inv = 1.f / lq;
+                const float inv = lq > 0.f ? 1.f / lq : 0.f;
 #pragma unroll
                 for (int f = 0; f < 4; ++f) orow[16 * f] = (bf16_t)to_bf16_bits(o[f][r] * inv);
             }
@@ -214,6 +217,13 @@ __device__ __forceinline__ bool span_merge_row(const SpanArgs& a, int item, int 
     return true;
 }
 
+// lse * log2(e) of a merged row for the key side, kLseGone if the sequence does not keep the node
+__device__ __forceinline__ float span_row_lse2(const SpanArgs& a, const SpanRow& r) {
+    int level, mi;
+    span_node_level(a.n, a.L, r.v, level, mi);
+    return (mi << level) < seq_length(a.seq_len, r.bh / a.H, a.n) ? a.lse_r[(int64_t)r.bh * a.N + r.v] * kLog2e : kLseGone;
+}
+
 __device__ __forceinline__ void fwd_span_merge_small(const SpanArgs& a, int item, int first, int rows) {
     const int lane = threadIdx.x & 63;
     SpanRow r;
@@ -237,8 +247,8 @@ __device__ __forceinline__ void fwd_span_merge_small(const SpanArgs& a, int item
         acc += o[b] * c;
     }
     const int64_t base = (int64_t)(r.bh / a.H) * a.sb + (int64_t)(r.bh % a.H) * a.sh;
-    a.out[base + (int64_t)r.v * a.sn + lane] = (bf16_t)to_bf16_bits(acc / ls);
-    if (lane == 0) a.lse[(int64_t)r.bh * a.N + r.v] = (mx + fast_log2(ls)) * kLn2;
+    a.out[base + (int64_t)r.v * a.sn + lane] = (bf16_t)to_bf16_bits(ls > 0.f ? acc / ls : 0.f);
+    if (lane == 0) a.lse[(int64_t)r.bh * a.N + r.v] = ls > 0.f ? (mx + fast_log2(ls)) * kLn2 : 0.f;
 }
 
 // one kernel for both kinds of rows: the first `small_blocks` workgroups take 16 short rows each
@@ -287,8 +297,8 @@ __global__ void __launch_bounds__(kSpanBigThreads) fwd_span_merge_kernel(const S
             lt += s_l[p];
         }
         const int64_t base = (int64_t)(r.bh / a.H) * a.sb + (int64_t)(r.bh % a.H) * a.sh;
-        a.out[base + (int64_t)r.v * a.sn + t] = (bf16_t)to_bf16_bits(sum / lt);
-        if (t == 0) a.lse[(int64_t)r.bh * a.N + r.v] = (mx + fast_log2(lt)) * kLn2;
+        a.out[base + (int64_t)r.v * a.sn + t] = (bf16_t)to_bf16_bits(lt > 0.f ? sum / lt : 0.f);
+        if (t == 0) a.lse[(int64_t)r.bh * a.N + r.v] = lt > 0.f ? (mx + fast_log2(lt)) * kLn2 : 0.f;
     }
 }
 
@@ -311,6 +321,7 @@ __global__ void __launch_bounds__(kTileThreads) bwd_q_span_tile_kernel(const Spa
     const float qscale = a.scale * kLog2e;
     const int ngroups = a.L > kSpanInLevels ? 3 : 2;
     const int nanc = a.L - kSpanInLevels;
+    const int len = seq_length(a.seq_len, bh / a.H, a.n);
 
     bf16x8_t ka[2][2], va[2][2];
 #pragma unroll
@@ -356,7 +367,7 @@ __global__ void __launch_bounds__(kTileThreads) bwd_q_span_tile_kernel(const Spa
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int tt = 16 * c + 4 * g + r;
-                const bool member = valid && (grp == 2 || (tt >> level) == loc);
+                const bool member = valid && (grp == 2 || (tt >> level) == loc) && t0 + tt < len;
                 p[c][r] = member ? fast_exp2(s4[r] * qscale + shift - lse2) : 0.f;
                 wgt[c][r] = p[c][r] * d4[r];
                 dl += wgt[c][r];
@@ -380,7 +391,8 @@ __global__ void __launch_bounds__(kTileThreads) bwd_q_span_tile_kernel(const Spa
                 dq[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sH, kB[f], dq[f], 0, 0, 0);
                 dq[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sL, kB[f], dq[f], 0, 0, 0);
             }
-            if (g == 0 && valid) a.stat[(int64_t)bh * a.N + node] = make_float2(lse2, dl);
+            if (g == 0 && valid)
+                a.stat[(int64_t)bh * a.N + node] = make_float2((((t0 >> level) + loc) << level) < len ? lse2 : kLseGone, dl);
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int slot = 4 * g + r;
@@ -450,7 +462,7 @@ __device__ __forceinline__ void bwd_q_span_merge_small(const SpanArgs& a, int it
         }
     const int64_t base = (int64_t)(r.bh / a.H) * a.sb + (int64_t)(r.bh % a.H) * a.sh;
     a.dQ[base + (int64_t)r.v * a.sn + lane] = a.scale * (sa - dl * sb);
-    if (lane == 0) a.stat[(int64_t)r.bh * a.N + r.v] = make_float2(a.lse_r[(int64_t)r.bh * a.N + r.v] * kLog2e, dl);
+    if (lane == 0) a.stat[(int64_t)r.bh * a.N + r.v] = make_float2(span_row_lse2(a, r), dl);
 }
 
 __global__ void __launch_bounds__(kSpanBigThreads) bwd_q_span_merge_kernel(const SpanArgs a, int first, int rows_small,
@@ -487,7 +499,7 @@ __global__ void __launch_bounds__(kSpanBigThreads) bwd_q_span_merge_kernel(const
         }
         const int64_t base = (int64_t)(r.bh / a.H) * a.sb + (int64_t)(r.bh % a.H) * a.sh;
         a.dQ[base + (int64_t)r.v * a.sn + t] = a.scale * (ta - td * tb);
-        if (t == 0) a.stat[(int64_t)r.bh * a.N + r.v] = make_float2(a.lse_r[(int64_t)r.bh * a.N + r.v] * kLog2e, td);
+        if (t == 0) a.stat[(int64_t)r.bh * a.N + r.v] = make_float2(span_row_lse2(a, r), td);
     }
 }
 

@@ -48,6 +48,9 @@ struct TileArgs {
     const float* lse_r;
     float* dQ;
     float2 *stat, *wp;
+    // sequences shorter than n
+    const int32_t *seq_len, *id_to_cid;
+    int32_t n, k, W, ctx_levels, causal;
 };
 
 __device__ __forceinline__ void wave_lds_sync() {  // order LDS traffic between the lanes of one wavefront
@@ -81,6 +84,32 @@ __device__ __forceinline__ bf16x8_t lds_transposed_b(const bf16_t* rows, int str
     typedef short s16x8_t __attribute__((ext_vector_type(8)));
     const s16x8_t xy = {x[0], x[1], x[2], x[3], y[0], y[1], y[2], y[3]};
     return __builtin_bit_cast(bf16x8_t, xy);
+}
+
+// Sequences shorter than n: the bias entries of edges such a sequence does not have are set to
+// kMaskBias, which drives their softmax weight to 0 without touching the loop over the chunks --
+// every entry of a token past the end, and for the other tokens the right-side nodes past the
+// end.  The i-th node to join on the right at level l is node p_l + i - 1 of that level, with
+// p_0 = t + 1 and p_{l+1} = ceil((p_l + k) / 2) (Algorithm 1: k nodes, one more when the run would
+// not end on a parent boundary), and level l keeps ceil(len / 2^l) nodes.  Lane (g, j) works on
+// token j of the tile; the four lane groups share the ids.
+constexpr float kMaskBias = -1.0e30f;
+__device__ __forceinline__ void mask_bias(const TileArgs& a, float* bias_s, int t0, int len, int g, int j) {
+    const int t = t0 + j;
+    float* row = bias_s + j * a.bias_stride;
+    if (t >= len) {
+        for (int c = 4 * g; c < a.cid_pad; c += 16) *reinterpret_cast<f32x4_t*>(row + c) = f32x4_t{kMaskBias, kMaskBias, kMaskBias, kMaskBias};
+    } else if (!a.causal) {
+        int p = t + 1;
+        for (int l = 0; l < a.ctx_levels; ++l) {
+            const int cnt = (len + (1 << l) - 1) >> l;            // nodes the level keeps
+            for (int o = max(cnt - p + 1, 1) + g; o <= a.k + 1; o += 4) {
+                const int cid = a.id_to_cid[l * a.W + a.k + 1 + o];
+                if (cid >= 0) row[cid] = kMaskBias;
+            }
+            p = (p + a.k + 1) >> 1;
+        }
+    }
 }
 
 // Position of a wavefront in its sequence of (token tile, pair of chunks); wave-uniform.
@@ -219,6 +248,10 @@ __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArg
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r1, qb1, acc, 0, 0, 0);
                 *reinterpret_cast<f32x4_t*>(bias_s + j * a.bias_stride + c + 4 * g) = acc;
             }
+            if (a.seq_len) {   // uniform
+                wave_lds_sync();
+                mask_bias(a, bias_s, cc.tile * 16, seq_length(a.seq_len, cc.bh / a.H, a.n), g, j);
+            }
         }
         wave_lds_sync();  // the previous pair's reads of k_s, v_s (and the previous tile's of bias_s) are done
 #pragma unroll
@@ -308,14 +341,15 @@ __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArg
         if (cc.pair == cc.npairs - 1) {   // the tile is complete
             const int64_t base = (int64_t)(cc.bh / a.H) * a.sb + (int64_t)(cc.bh % a.H) * a.sh;
             const int t0 = cc.tile * 16;
+            const int len = seq_length(a.seq_len, cc.bh / a.H, a.n);   // tokens past the end give zeros
             // row sums: token j is spread over the 4 lane groups
             float l = l_part + __shfl_xor(l_part, 16);
             l += __shfl_xor(l, 32);
-            if (g == 0) a.lse[(int64_t)cc.bh * a.N + t0 + j] = (m_run + fast_log2(l)) * kLn2;
+            if (g == 0) a.lse[(int64_t)cc.bh * a.N + t0 + j] = t0 + j < len ? (m_run + fast_log2(l)) * kLn2 : 0.f;
             bf16_t* orow = a.out + base + (int64_t)t0 * a.sn + j;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const float inv = 1.f / __shfl(l, 4 * g + r);
+                const float inv = t0 + 4 * g + r < len ? 1.f / __shfl(l, 4 * g + r) : 0.f;
 #pragma unroll
                 for (int f = 0; f < 4; ++f)
                     orow[(int64_t)(4 * g + r) * a.sn + 16 * f] = (bf16_t)to_bf16_bits(o[f][r] * inv);
@@ -469,6 +503,10 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_q_tile_kernel(const TileA
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r1, qb1, acc, 0, 0, 0);
                 *reinterpret_cast<f32x4_t*>(bias_s + j * a.bias_stride + c + 4 * g) = acc;
             }
+            if (a.seq_len) {   // uniform
+                wave_lds_sync();
+                mask_bias(a, bias_s, cc.tile * 16, seq_length(a.seq_len, cc.bh / a.H, a.n), g, j);
+            }
         }
         wave_lds_sync();  // the previous pair's reads of k_s, v_s (and the previous tile's of bias_s) are done
 #pragma unroll
@@ -560,7 +598,8 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_q_tile_kernel(const TileA
             const int t0 = cc.tile * 16;
             float delta = dl_part + __shfl_xor(dl_part, 16);
             delta += __shfl_xor(delta, 32);
-            if (g == 0) a.stat[(int64_t)cc.bh * a.N + t0 + j] = make_float2(lse2, delta);
+            const int len = seq_length(a.seq_len, cc.bh / a.H, a.n);
+            if (g == 0) a.stat[(int64_t)cc.bh * a.N + t0 + j] = make_float2(t0 + j < len ? lse2 : kLseGone, delta);
             float* qrow_out = a.dQ + base + (int64_t)t0 * a.sn + j;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {

@@ -118,6 +118,8 @@ void fill_common(AttnArgs& a, const bpt_graph* g, const bpt_shape_t* s) {
     a.row_bytes = (int32_t)(s->stride_n * es);
     a.slab_bytes = (uint32_t)(((int64_t)(g->num_nodes - 1) * s->stride_n + kD) * es);
     a.idx_bytes = (uint32_t)(g->num_edges * 4);
+    a.seq_len = s->seq_len;
+    a.lg = g->num_levels - 1;
 }
 
 void use_schedule(AttnArgs& a, const Schedule& sc) {
@@ -202,6 +204,13 @@ void fill_tile_args(TileArgs& t, const bpt_graph* g, const AttnArgs& a, const Ti
     t.bias_stride = tp.bias_stride;
     t.row_bytes = a.row_bytes;
     t.slab_bytes = a.slab_bytes;
+    t.seq_len = a.seq_len;
+    t.id_to_cid = g->tiles.id_to_cid;
+    t.n = g->n;
+    t.k = g->k;
+    t.W = g->rel_width;
+    t.ctx_levels = g->ctx_levels;
+    t.causal = g->causal;
 }
 
 // Span rows on blocks of 32 tokens (fwd_span_tile_kernel, bwd_q_span_tile_kernel): needs the token
@@ -239,6 +248,7 @@ void fill_span_args(SpanArgs& t, const bpt_graph* g, const AttnArgs& a) {
     t.W = g->rel_width;
     t.zero = g->k + 1;
     t.scale = a.scale;
+    t.seq_len = a.seq_len;
 }
 // forward == true: out and lse of all span rows; else delta, lse and dQ of all span rows
 int run_span_tiles(const bpt_graph* g, const AttnArgs& a, bool forward, hipStream_t st) {
@@ -543,6 +553,8 @@ int run_bwd_kv_tiles(const bpt_graph* g, const BwdPlan& p, const AttnArgs& a, co
     t.W = g->rel_width;
     t.zero = g->k + 1;
     t.num_chunks = kt.num_chunks;
+    t.seq_len = a.seq_len;
+    t.n = g->n;
     int rc = BPT_ERR_UNSUPPORTED;
     switch (kt.nb_pad / 16) {
         case 1: rc = launch_kv_tiles<1>(t, p, lim, st); break;

@@ -69,9 +69,10 @@ def test_null_graph_is_an_error_everywhere():
 
 
 def test_shape_struct_layout_matches_the_header():
-    # int32 B,H,D,dtype; int64 stride_b,stride_h,stride_n; float scale (+ tail padding)
-    assert ctypes.sizeof(bpt.BptShape) == 48
+    # int32 B,H,D,dtype; int64 stride_b,stride_h,stride_n; float scale (+ padding); pointer seq_len
+    assert ctypes.sizeof(bpt.BptShape) == 56
     assert bpt.BptShape.stride_b.offset == 16 and bpt.BptShape.scale.offset == 40
+    assert bpt.BptShape.seq_len.offset == 48
 
 
 def test_no_cpu_fallback_when_the_library_is_missing(monkeypatch, tmp_path):

@@ -169,6 +169,92 @@ def test_full_size_configuration(name):
     run_case(WORKLOADS[name])
 
 
+def run_lengths_case(w: Workload, lengths, poison=50.0):
+    """A batch whose b-th sequence has lengths[b] <= n tokens: GPU (seq_len argument) against the oracle
+    run per batch entry on the graph of that length.  Input rows of nodes that are not kept are
+    multiplied by `poison`: they must not matter, and their outputs must be zero."""
+    say("lengths case", w, list(lengths))
+    assert len(lengths) == w.B
+    x = make_inputs(w)
+    for b, length in enumerate(lengths):
+        if length >= 1:
+            gone = np.flatnonzero(np.diff(oracle.build_graph_len(w.n, int(length), w.k, w.causal).row_ptr) == 0)
+        else:
+            gone = np.arange(2 * w.n - 1)
+        for key in ("Q", "K", "V", "dO"):
+            x[key][b][:, gone] *= np.float32(poison)
+            if w.dtype == "bf16":                             # keep the values bf16-representable
+                x[key][b][:, gone] = torch.from_numpy(x[key][b][:, gone]).to(torch.bfloat16).float().numpy()
+    g = bpt.bpt_build_graph(w.n, w.k, w.causal)
+    Q, K, V, dO, R = (to_dev(x[k], w.dtype) for k in ("Q", "K", "V", "dO", "Rel"))
+    lens_d = torch.tensor(list(lengths), dtype=torch.int32, device="cuda")
+    out_d, lse_d = bpt.bpt_attn_fwd(g, Q, K, V, R, scale=w.scale, seq_len=lens_d)
+    grads = bpt.bpt_attn_bwd(g, Q, K, V, R, lse_d, dO, scale=w.scale, seq_len=lens_d)
+    torch.cuda.synchronize()
+    live = [b for b, length in enumerate(lengths) if length >= 1]
+    ref = {k: np.zeros(x["Q"].shape) for k in ("out", "dQ", "dK", "dV")}
+    ref["lse"] = np.zeros(x["Q"].shape[:3])
+    ref["d_rel"] = np.zeros(x["Rel"].shape)
+    if live:
+        sub = {k: np.ascontiguousarray(x[k][live]) for k in ("Q", "K", "V", "dO")}
+        ll = [lengths[b] for b in live]
+        o, l, _ = oracle.attn_fwd_lengths(w.n, w.k, w.causal, ll, sub["Q"], sub["K"], sub["V"], x["Rel"], w.scale)
+        dq, dk, dv, dr = oracle.attn_bwd_lengths(w.n, w.k, w.causal, ll, sub["Q"], sub["K"], sub["V"], x["Rel"],
+                                                 sub["dO"], w.scale)
+        ref["out"][live], ref["lse"][live], ref["dQ"][live], ref["dK"][live], ref["dV"][live] = o, l, dq, dk, dv
+        ref["d_rel"] = dr
+    res = {}
+    for name, got_t in zip(("out", "lse", "dQ", "dK", "dV", "d_rel"), (out_d, lse_d) + tuple(grads)):
+        got = host(got_t)
+        assert np.isfinite(got).all(), name
+        err = float(np.abs(got - ref[name]).max())
+        res[name] = err
+        assert err <= TOL[w.dtype], (name, err)
+    # rows of nodes that are not kept: exact zeros
+    for b, length in enumerate(lengths):
+        deg = np.diff(oracle.build_graph_len(w.n, max(int(length), 1), w.k, w.causal).row_ptr)
+        gone = np.flatnonzero(deg == 0) if length >= 1 else np.arange(2 * w.n - 1)
+        for name, got_t in zip(("out", "lse", "dQ", "dK", "dV"), (out_d, lse_d) + tuple(grads[:3])):
+            assert float(host(got_t)[b][:, gone].__abs__().max(initial=0.0)) == 0.0, (name, b)
+    say("   max-abs errors", {k: float("%.3g" % v) for k, v in res.items()})
+    g.destroy()
+
+
+LENGTHS = [
+    # fp32: gather kernels
+    ("f32", 8, 1, False, 1, [8, 1, 5, 3]), ("f32", 64, 2, False, 2, [64, 1, 37, 17]), ("f32", 256, 3, True, 1, [100, 256, 2]),
+    ("f32", 2048, 5, False, 1, [1500, 700]),
+    # bf16 below the tile sizes, and around the switches of the tile kernels
+    ("bf16", 8, 2, False, 1, [5, 8]), ("bf16", 16, 1, False, 2, [16, 9, 1]), ("bf16", 32, 1, True, 1, [31, 17, 32]),
+    ("bf16", 64, 2, False, 1, [33, 64, 2, 48]),
+    # bf16 tile kernels: ragged ends inside a tile, a whole sequence of one token, an empty one
+    ("bf16", 512, 4, False, 2, [512, 300, 33, 1, 0]), ("bf16", 1024, 3, True, 2, [1000, 17, 1024]),
+    ("bf16", 2048, 16, False, 1, [2047, 1025]), ("bf16", 4096, 8, True, 1, [3000, 4096, 129]),
+    ("bf16", 4096, 40, False, 1, [2500]),
+]
+
+
+@pytest.mark.parametrize("dtype,n,k,causal,H,lengths", LENGTHS)
+def test_sequences_of_different_lengths(dtype, n, k, causal, H, lengths):
+    w = Workload("lengths", 21, n, k, causal, len(lengths), H, 64, dtype, True)
+    run_lengths_case(w, lengths)
+
+
+def test_lengths_equal_to_n_change_nothing():
+    w = Workload("full_lengths", 22, 1024, 4, False, 2, 2, 64, "bf16", True)
+    x = make_inputs(w)
+    g = bpt.bpt_build_graph(w.n, w.k, w.causal)
+    Q, K, V, dO, R = (to_dev(x[k], w.dtype) for k in ("Q", "K", "V", "dO", "Rel"))
+    lens_d = torch.full((w.B,), w.n, dtype=torch.int32, device="cuda")
+    a = bpt.bpt_attn_fwd(g, Q, K, V, R, scale=w.scale)
+    b = bpt.bpt_attn_fwd(g, Q, K, V, R, scale=w.scale, seq_len=lens_d)
+    ga = bpt.bpt_attn_bwd(g, Q, K, V, R, a[1], dO, scale=w.scale)
+    gb = bpt.bpt_attn_bwd(g, Q, K, V, R, b[1], dO, scale=w.scale, seq_len=lens_d)
+    for s, t in zip(a + tuple(ga), b + tuple(gb)):
+        assert torch.equal(s, t)
+    g.destroy()
+
+
 def test_scale_argument_and_default():
     w = Workload("scale", 10, 256, 2, False, 1, 2, 64, "f32", True)
     x = make_inputs(w)
