@@ -73,7 +73,7 @@ def main():
         return
 
     from paper_1911_04070_amd import binding as bpt
-    from paper_1911_04070_amd.workloads import WORKLOADS, make_inputs
+    from paper_1911_04070_amd.workloads import WORKLOADS, make_inputs, make_lengths
 
     if not os.path.exists(bpt.LIB_PATH):
         from paper_1911_04070_amd.build import build_library
@@ -94,7 +94,13 @@ def main():
     g = bpt.bpt_build_graph(w.n, w.k, w.causal)
     torch.cuda.synchronize()
     build_ms = (time.perf_counter() - t0) * 1e3
-    edge_inst = w.B * w.H * g.num_edges
+    # sequences of different lengths: only the edges a sequence keeps count as work
+    lengths = make_lengths(w) if w.length_mix else None
+    lens_d = torch.from_numpy(lengths).cuda() if lengths is not None else None
+    if lengths is None:
+        edge_inst = w.B * w.H * g.num_edges
+    else:
+        edge_inst = w.H * sum(bpt.bpt_count_edges(w.n, w.k, w.causal, int(x)) for x in lengths)
 
     Q, K, V, R, dO = dev["Q"], dev["K"], dev["V"], dev["Rel"], dev["dO"]
     out = torch.empty_like(Q)
@@ -106,9 +112,9 @@ def main():
     ws_b = torch.empty(max(bws, 256), dtype=torch.uint8, device="cuda")
 
     def step():
-        bpt.bpt_attn_fwd(g, Q, K, V, R, scale=w.scale, out=out, lse=lse, workspace=ws_f)
+        bpt.bpt_attn_fwd(g, Q, K, V, R, scale=w.scale, out=out, lse=lse, workspace=ws_f, seq_len=lens_d)
         if w.backward:
-            bpt.bpt_attn_bwd(g, Q, K, V, R, lse, dO, scale=w.scale, grads=grads, workspace=ws_b)
+            bpt.bpt_attn_bwd(g, Q, K, V, R, lse, dO, scale=w.scale, grads=grads, workspace=ws_b, seq_len=lens_d)
 
     for _ in range(args.warmup):
         step()
@@ -131,12 +137,14 @@ def main():
 
     reps = max(5, min(args.steps, 30))
     stage_ms = {"fwd": timed(lambda: bpt.bpt_attn_fwd(g, Q, K, V, R, scale=w.scale, out=out, lse=lse,
-                                                      workspace=ws_f), reps)}
+                                                      workspace=ws_f, seq_len=lens_d), reps)}
     if w.backward:
         stage_ms["bwd_query_side"] = timed(
-            lambda: bpt.bpt_attn_bwd_query_side(g, Q, K, V, R, lse, dO, grads[0], grads[3], ws_b, scale=w.scale), reps)
+            lambda: bpt.bpt_attn_bwd_query_side(g, Q, K, V, R, lse, dO, grads[0], grads[3], ws_b, scale=w.scale,
+                                                seq_len=lens_d), reps)
         stage_ms["bwd_key_side"] = timed(
-            lambda: bpt.bpt_attn_bwd_key_side(g, Q, K, V, R, lse, dO, grads[1], grads[2], ws_b, scale=w.scale), reps)
+            lambda: bpt.bpt_attn_bwd_key_side(g, Q, K, V, R, lse, dO, grads[1], grads[2], ws_b, scale=w.scale,
+                                              seq_len=lens_d), reps)
 
     # per-kernel device time, live: the library brackets each of its launches with HIP events on the launch stream
     bpt.bpt_profile_enable(True)
@@ -149,22 +157,23 @@ def main():
 
     # algorithmic bytes per launch: every edge-instance a gather kernel handles counts one
     # key row + one value row (or one query row + one dout row): 256 B in bf16, 512 B in fp32
-    e_tok = int(g.csr_to_host()[0][w.n])
-    e_span = g.num_edges - e_tok
     bh = w.B * w.H
+    if lengths is None:
+        tok_inst = int(g.csr_to_host()[0][w.n]) * bh
+    else:   # every level above the tokens holds each token of a sequence once
+        tok_inst = edge_inst - w.H * int(lengths.sum()) * (g.num_levels - 1)
+    span_inst = edge_inst - tok_inst
     gather = 256.0 * bytes_scale
     alg_bytes = {
-        "fwd_tile_kernel": gather * e_tok * bh, "bwd_q_tile_kernel": gather * e_tok * bh,
-        "fwd_span_tile_kernel": gather * e_span * bh, "bwd_q_span_tile_kernel": gather * e_span * bh,
-        "bwd_kv_tile_kernel": gather * g.num_edges * bh, "bwd_kv_kernel": gather * g.num_edges * bh,
+        "fwd_tile_kernel": gather * tok_inst, "bwd_q_tile_kernel": gather * tok_inst,
+        "fwd_span_tile_kernel": gather * span_inst, "bwd_q_span_tile_kernel": gather * span_inst,
+        "bwd_kv_tile_kernel": gather * edge_inst, "bwd_kv_kernel": gather * edge_inst,
     }
     # the gather kernels take whatever rows the tile kernels of this launch did not
-    fwd_rest = g.num_edges - (e_tok if "fwd_tile_kernel" in kernel_ms else 0) - (
-        e_span if "fwd_span_tile_kernel" in kernel_ms else 0)
-    bwd_rest = g.num_edges - (e_tok if "bwd_q_tile_kernel" in kernel_ms else 0) - (
-        e_span if "bwd_q_span_tile_kernel" in kernel_ms else 0)
-    alg_bytes["fwd_kernel"] = gather * fwd_rest * bh
-    alg_bytes["bwd_q_kernel"] = gather * bwd_rest * bh
+    alg_bytes["fwd_kernel"] = gather * (edge_inst - (tok_inst if "fwd_tile_kernel" in kernel_ms else 0) - (
+        span_inst if "fwd_span_tile_kernel" in kernel_ms else 0))
+    alg_bytes["bwd_q_kernel"] = gather * (edge_inst - (tok_inst if "bwd_q_tile_kernel" in kernel_ms else 0) - (
+        span_inst if "bwd_q_span_tile_kernel" in kernel_ms else 0))
     main = {k: v for k, v in kernel_ms.items() if k in alg_bytes}
     dominant = max(main, key=main.get)
     achieved = alg_bytes[dominant] / (kernel_ms[dominant] * 1e-3) / 1e9
@@ -202,8 +211,14 @@ def main():
         passes, dt, used = 0, 0.0, 1
         while passes < 1 or (dt < 5.0 and passes < 50):      # a few seconds of wall time on all cores
             t0 = time.perf_counter()
-            _, _, used = oracle.attn_fwd(og, x["Q"], x["K"], x["V"], x["Rel"], w.scale)
-            if w.backward:
+            if lengths is not None:
+                oracle.attn_fwd_lengths(w.n, w.k, w.causal, lengths, x["Q"], x["K"], x["V"], x["Rel"], w.scale)
+                if w.backward:
+                    oracle.attn_bwd_lengths(w.n, w.k, w.causal, lengths, x["Q"], x["K"], x["V"], x["Rel"], x["dO"], w.scale)
+                used = min(os.cpu_count() or 1, w.H)
+            else:
+                _, _, used = oracle.attn_fwd(og, x["Q"], x["K"], x["V"], x["Rel"], w.scale)
+            if w.backward and lengths is None:
                 oracle.attn_bwd(og, x["Q"], x["K"], x["V"], x["Rel"], x["dO"], w.scale)
             dt += time.perf_counter() - t0
             passes += 1
@@ -220,7 +235,8 @@ def main():
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "n": w.n, "k": w.k, "causal": w.causal, "batch": w.B, "heads": w.H,
                    "head_dim": w.D, "nodes": g.num_nodes, "edges": g.num_edges, "edge_instances": edge_inst,
-                   "backward": w.backward},
+                   "backward": w.backward,
+                   "lengths": ([int(v) for v in lengths] if lengths is not None else None)},
         "graph_build_ms": round(build_ms, 3),
         "edges_per_s_incl_build": round(edge_inst / ((ms_per_step + build_ms) * 1e-3), 1),
         "roofline": roofline,

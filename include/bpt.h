@@ -167,6 +167,14 @@ int bpt_attn_bwd_key_side(const bpt_graph_t* g, const bpt_shape_t* s, const void
 int bpt_profile_enable(int on);
 int64_t bpt_profile_report(char* buf, size_t capacity);
 
+/* Sec. 3.2 with the rule for shorter sequences stated at the top of this header: the number
+ * of edges of the graph over n tokens with density k that a sequence of len tokens keeps
+ * (0 <= len <= n; len == n gives the graph's own edge count).  Host arithmetic only, no
+ * device is touched; O(len log n).  The throughput of a batch of sequences of different
+ * lengths is counted in these edges.  BPT_ERR_INVALID_ARG / BPT_ERR_UNSUPPORTED as for
+ * bpt_build_graph, or if len is out of range. */
+int bpt_count_edges(int32_t n, int32_t k, int32_t causal, int32_t len, int64_t* edges);
+
 /* Static, never NULL. */
 const char* bpt_strerror(int status);
 

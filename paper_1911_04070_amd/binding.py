@@ -23,7 +23,7 @@ EXPORTS = [
     "bpt_build_graph", "bpt_graph_info", "bpt_graph_csr", "bpt_graph_transposed", "bpt_graph_to_host",
     "bpt_graph_transposed_to_host", "bpt_graph_destroy", "bpt_attn_fwd_workspace", "bpt_attn_bwd_workspace",
     "bpt_attn_fwd", "bpt_attn_bwd", "bpt_attn_bwd_query_side", "bpt_attn_bwd_key_side", "bpt_profile_enable",
-    "bpt_profile_report", "bpt_strerror",
+    "bpt_profile_report", "bpt_count_edges", "bpt_strerror",
 ]
 
 
@@ -84,6 +84,8 @@ def load_library() -> ctypes.CDLL:
     L.bpt_profile_enable.argtypes = [ctypes.c_int]
     L.bpt_profile_report.restype = ctypes.c_int64
     L.bpt_profile_report.argtypes = [ctypes.c_char_p, sz]
+    L.bpt_count_edges.restype = ctypes.c_int
+    L.bpt_count_edges.argtypes = [i32, i32, i32, i32, P(i64)]
     L.bpt_strerror.restype = ctypes.c_char_p
     L.bpt_strerror.argtypes = [ctypes.c_int]
     _lib = L
@@ -161,6 +163,13 @@ class Graph:
                "bpt_graph_transposed")
         return {"row_ptr": a.value, "col": b.value, "rel": c.value, "t_ptr": d.value, "t_src": e.value,
                 "t_eid": f.value}
+
+
+def bpt_count_edges(n: int, k: int, causal: bool, length: int) -> int:
+    """Edges of the graph over n tokens that a sequence of `length` tokens keeps (host arithmetic)."""
+    out = ctypes.c_int64()
+    _check(load_library().bpt_count_edges(n, k, int(bool(causal)), int(length), ctypes.byref(out)), "bpt_count_edges")
+    return int(out.value)
 
 
 def bpt_build_graph(n: int, k: int, causal: bool) -> Graph:

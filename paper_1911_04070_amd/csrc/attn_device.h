@@ -58,6 +58,25 @@ __device__ __forceinline__ int node_first_token(int id, int lg) {
     const int level = lg - (31 - __clz(x - 1));
     return (((2 << lg) >> level) - x) << level;
 }
+// The walk over (batch*head, tile) gives every XCD a contiguous share.  With sequences of
+// different lengths the shares are cut head-major (all batch entries of a head together), so that
+// every XCD gets the same mix of lengths instead of a few whole batch entries.
+__device__ __forceinline__ int walk_bh(const int32_t* seq_len, int idx, int BH, int H) {
+    if (!seq_len) return idx;
+    const int B = BH / H;
+    return (idx % B) * H + idx / B;
+}
+// A persistent workgroup steps through the work items with a stride that usually divides the
+// number of items per (batch, head), so it would meet the same positions of every sequence -- and a
+// workgroup on the late positions would find most of them past the end.  With sequences of different
+// lengths the positions are therefore rotated by a different amount for every (batch, head).
+__device__ __forceinline__ int walk_pos(const int32_t* seq_len, int slab, int pos, int count) {
+    if (!seq_len) return pos;
+    // fractional part of slab * golden ratio, scaled to the item count: rotations of consecutive
+    // (batch, head)s are spread evenly, so a workgroup's positions cover the sequences evenly
+    const unsigned rot = (unsigned)(((unsigned long long)((unsigned)slab * 0x9E3779B1u) * (unsigned)count) >> 32);
+    return (int)(((unsigned)pos + rot) % (unsigned)count);
+}
 constexpr float kLseGone = 1.0e30f;   // stands for lse * log2(e) of a row that is not kept: exp2(s - kLseGone) = 0
 
 // ---- lane helpers ---------------------------------------------------------------

@@ -57,10 +57,11 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyA
     const rsrc_t rM = make_rsrc(a.map, (uint32_t)a.num_chunks * 512u);    // [chunks][16][16] int16
 
     for (TileWalk w(a.BH * groups); w.t < w.t_end; w.t += w.step) {
-        const int bh = w.t / groups;
-        const int task = (w.t - bh * groups) * kTileWaves + wave;
+        const int slab = w.t / groups;
+        const int bh = walk_bh(a.seq_len, slab, a.BH, a.H);
+        const int task = walk_pos(a.seq_len, slab, w.t - slab * groups, groups) * kTileWaves + wave;
         if (task >= a.num_tasks) continue;
-        const int kt = a.task_tile[task], c0 = a.task_c0[task], nch = a.task_nch[task], part = a.task_part[task];
+        const int kt = a.task_tile[task], c0 = a.task_c0[task], part = a.task_part[task];
         const int node0 = a.tile_node0[kt], info = a.tile_info[kt];
         const int level = info & 255, nkeys = info >> 8;
         // a shorter sequence keeps the first ceil(len / 2^level) nodes of the level; queries that are
@@ -68,7 +69,10 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyA
         const int len = seq_length(a.seq_len, bh / a.H, a.n);
         const int kept_keys = ((len + (1 << level) - 1) >> level) - (node0 - (2 * a.n - ((2 * a.n) >> level)));
         const bool key_kept = j < kept_keys;
+        const int nch = a.task_nch[task];
         const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
+        // wave-uniform: no key of the tile exists in this sequence; kv_tile_merge_kernel writes the zero rows
+        if (kept_keys <= 0) continue;
         const rsrc_t rQ = make_rsrc(a.Q + base, a.slab_bytes), rG = make_rsrc(a.dout + base, a.slab_bytes);
         const rsrc_t rS = make_rsrc(a.stat + (int64_t)bh * a.N, (uint32_t)a.N * 8u);
 
@@ -267,25 +271,38 @@ __global__ void __launch_bounds__(256) kv_tile_merge_kernel(const KeyArgs a, con
                                                             int first_zero) {
     const int merge_blocks = a.BH * num_multi;
     if ((int)blockIdx.x >= merge_blocks) {
-        const int rows = a.N - first_zero;
+        // zero rows: without seq_len the nodes from first_zero on, 64 threads per row; with seq_len
+        // every node is looked at, 16 threads per row, and those a shorter sequence does not keep
+        // (which the tile kernel steps over) are written as well
+        const int row0 = a.seq_len ? 0 : first_zero, rows = a.N - row0;
+        const int per_row = a.seq_len ? 16 : 64;
         const int64_t i = (int64_t)(blockIdx.x - merge_blocks) * blockDim.x + threadIdx.x;
-        if (i >= (int64_t)a.BH * rows * kD) return;
-        const int f = (int)(i & 63);
-        const int64_t rr = i >> 6;
-        const int bh = (int)(rr / rows), row = first_zero + (int)(rr - (int64_t)bh * rows);
-        const int64_t at = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh + (int64_t)row * a.sn + f;
-        a.dK[at] = 0.f;
-        a.dV[at] = 0.f;
+        if (i >= (int64_t)a.BH * rows * per_row) return;
+        const int64_t rr = i / per_row;
+        const int bh = (int)(rr / rows), row = row0 + (int)(rr - (int64_t)bh * rows);
+        const int64_t at = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh + (int64_t)row * a.sn;
+        if (!a.seq_len) {
+            const int f = (int)(i & 63);
+            a.dK[at + f] = 0.f;
+            a.dV[at + f] = 0.f;
+        } else if (row >= first_zero || node_first_token(row, 31 - __clz(a.n)) >= seq_length(a.seq_len, bh / a.H, a.n)) {
+            const int f = (int)(i & 15) * 4;
+            *reinterpret_cast<float4*>(a.dK + at + f) = make_float4(0.f, 0.f, 0.f, 0.f);
+            *reinterpret_cast<float4*>(a.dV + at + f) = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
         return;
     }
     const int bh = blockIdx.x / num_multi, mt = blockIdx.x - bh * num_multi;
     const int kt = multi_tile[mt];
-    const int node0 = a.tile_node0[kt], nkeys = a.tile_info[kt] >> 8;
+    const int node0 = a.tile_node0[kt], nkeys = a.tile_info[kt] >> 8, level = a.tile_info[kt] & 255;
     const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
+    // a tile none of whose keys exists in this (shorter) sequence has no partial sums: zeros
+    const int len = seq_length(a.seq_len, bh / a.H, a.n);
+    const bool gone = ((len + (1 << level) - 1) >> level) - (node0 - (2 * a.n - ((2 * a.n) >> level))) <= 0;
     for (int i = threadIdx.x; i < nkeys * kD; i += blockDim.x) {
         const int key = i >> 6, f = i & 63;
         float sk = 0.f, sv = 0.f;
-        for (int p = multi_ptr[mt]; p < multi_ptr[mt + 1]; ++p) {
+        for (int p = gone ? multi_ptr[mt + 1] : multi_ptr[mt]; p < multi_ptr[mt + 1]; ++p) {
             const float* src = a.part + (((int64_t)bh * a.num_part + p) * 16 + key) * (2 * kD) + f;
             sk += src[0];
             sv += src[kD];

@@ -153,19 +153,30 @@ __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArg
 
     // One sequence of pairs of chunks through the wavefront's tiles, software pipelined as in
     // bwd_q_tile_kernel: `cc` is computed, the rows of `cr` and the ids of `ci` are in flight.
+    // A tile whose 16 tokens all lie past the end of a shorter sequence is not computed: whoever
+    // walks over it (every tile is entered by exactly one cursor, the others are copies) writes
+    // its zero rows.
     auto enter_tile = [&](TileCursor& c) {
         c.valid = false;
         c.pair = 0;
         c.npairs = 1;
         for (; c.t < w.t_end; c.t += w.step) {
-            c.bh = c.t / groups_per_bh;
-            c.tile = (c.t - c.bh * groups_per_bh) * kTileWaves + wave;
-            if (c.tile < a.num_tiles) {
-                c.cp0 = a.chunk_ptr[c.tile];
-                c.npairs = (a.chunk_ptr[c.tile + 1] - c.cp0) >> 1;
-                c.valid = true;
-                return;
+            const int slab = c.t / groups_per_bh;
+            c.bh = walk_bh(a.seq_len, slab, a.BH, a.H);
+            c.tile = walk_pos(a.seq_len, slab, c.t - slab * groups_per_bh, groups_per_bh) * kTileWaves + wave;
+            if (c.tile >= a.num_tiles) continue;
+            if (a.seq_len && c.tile * 16 >= seq_length(a.seq_len, c.bh / a.H, a.n)) {
+                const int64_t base = (int64_t)(c.bh / a.H) * a.sb + (int64_t)(c.bh % a.H) * a.sh;
+                bf16_t* orow = a.out + base + (int64_t)(c.tile * 16 + r8) * a.sn + piece * 8;
+                *reinterpret_cast<uint4*>(orow) = make_uint4(0u, 0u, 0u, 0u);
+                *reinterpret_cast<uint4*>(orow + 8 * a.sn) = make_uint4(0u, 0u, 0u, 0u);
+                if (lane < 16) a.lse[(int64_t)c.bh * a.N + c.tile * 16 + lane] = 0.f;
+                continue;
             }
+            c.cp0 = a.chunk_ptr[c.tile];
+            c.npairs = (a.chunk_ptr[c.tile + 1] - c.cp0) >> 1;
+            c.valid = true;
+            return;
         }
     };
     auto advance = [&](TileCursor& c) {
@@ -403,19 +414,33 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_q_tile_kernel(const TileA
     // The wavefront's work is one sequence of pairs of chunks running through its tiles.
     // Three positions move along it: `cc` is computed, the rows of `cr` (one pair ahead) are
     // in flight, the column ids and map words of `ci` (two pairs ahead) are in flight.
+    // Tiles past the end of a shorter sequence are not computed (see fwd_tile_kernel): zero dQ rows,
+    // and `stat` entries that switch the rows off on the key side; their (w, p) slots stay unwritten
+    // and rel_grad_tile_kernel does not read them.
     auto enter_tile = [&](TileCursor& c) {
         c.valid = false;
         c.pair = 0;
         c.npairs = 1;
         for (; c.t < w.t_end; c.t += w.step) {
-            c.bh = c.t / groups_per_bh;
-            c.tile = (c.t - c.bh * groups_per_bh) * kTileWaves + wave;
-            if (c.tile < a.num_tiles) {
-                c.cp0 = a.chunk_ptr[c.tile];
-                c.npairs = (a.chunk_ptr[c.tile + 1] - c.cp0) >> 1;
-                c.valid = true;
-                return;
+            const int slab = c.t / groups_per_bh;
+            c.bh = walk_bh(a.seq_len, slab, a.BH, a.H);
+            c.tile = walk_pos(a.seq_len, slab, c.t - slab * groups_per_bh, groups_per_bh) * kTileWaves + wave;
+            if (c.tile >= a.num_tiles) continue;
+            if (a.seq_len && c.tile * 16 >= seq_length(a.seq_len, c.bh / a.H, a.n)) {
+                const int64_t base = (int64_t)(c.bh / a.H) * a.sb + (int64_t)(c.bh % a.H) * a.sh;
+                float* qrow = a.dQ + base + (int64_t)(c.tile * 16 + r8) * a.sn + piece * 8;
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    *reinterpret_cast<float4*>(qrow + (int64_t)8 * h * a.sn) = make_float4(0.f, 0.f, 0.f, 0.f);
+                    *reinterpret_cast<float4*>(qrow + (int64_t)8 * h * a.sn + 4) = make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+                if (lane < 16) a.stat[(int64_t)c.bh * a.N + c.tile * 16 + lane] = make_float2(kLseGone, 0.f);
+                continue;
             }
+            c.cp0 = a.chunk_ptr[c.tile];
+            c.npairs = (a.chunk_ptr[c.tile + 1] - c.cp0) >> 1;
+            c.valid = true;
+            return;
         }
     };
     auto advance = [&](TileCursor& c) {
@@ -636,6 +661,7 @@ struct RelGradArgs {
     int64_t sb, sh, sn;
     int32_t BH, H, N, n, num_tiles, num_chunks, num_cids, nids;   // nids = ids padded to 32
     float scale;
+    const int32_t* seq_len;   // [B] tokens of every sequence, or null
 };
 // 8 consecutive k of the operand row/column `col0 + j`: two transposing reads of 4 rows each
 __device__ __forceinline__ bf16x8_t lds_tr8(const bf16_t* base, int stride, int row0, int col0, int j) {
@@ -652,7 +678,7 @@ constexpr int kRgPrefetch = 8;   // tile slots per thread fetched one block ahea
 constexpr int kRgTileMaxIds = 512;
 // CPW: 16-id chunks per wavefront (2: up to 256 ids, 4: up to 512)
 template <int CPW>
-__global__ void __launch_bounds__(kThreads) rel_grad_tile_kernel(const RelGradArgs a) {
+__global__ void __launch_bounds__(kThreads, CPW == 2 ? 4 : 2) rel_grad_tile_kernel(const RelGradArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int nids = a.nids;
     bf16_t* ds_hi = reinterpret_cast<bf16_t*>(smem);                 // [nids][kRgStride]: DS^T, rows of the block along a line
@@ -690,11 +716,13 @@ __global__ void __launch_bounds__(kThreads) rel_grad_tile_kernel(const RelGradAr
     float2 wpv[kRgPrefetch];
     int s_begin = 0, s_mid = 0, s_end = 0;   // first slot of the block, of its second tile, and the end
     auto prefetch = [&](int blk) {
-        const int bh = blk / blocks_per_bh, b2 = 2 * (blk - bh * blocks_per_bh), row0 = 16 * b2;
+        const int bh = blk / blocks_per_bh, b2 = 2 * walk_pos(a.seq_len, bh, blk - bh * blocks_per_bh, blocks_per_bh), row0 = 16 * b2;
         const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
+        // token tiles past the end of a shorter sequence were not computed: their slots do not count
+        const int len = seq_length(a.seq_len, bh / a.H, a.n);
         s_begin = a.chunk_ptr[b2] * 256;
         s_mid = a.chunk_ptr[min(b2 + 1, a.num_tiles)] * 256;
-        s_end = a.chunk_ptr[min(b2 + 2, a.num_tiles)] * 256;
+        s_end = row0 + 16 < len ? a.chunk_ptr[min(b2 + 2, a.num_tiles)] * 256 : s_mid;
         qpiece = make_uint4(0u, 0u, 0u, 0u);
         if (threadIdx.x < kRgRows * 8) {
             const int r = threadIdx.x >> 3, c = (threadIdx.x & 7) * 8;
@@ -712,10 +740,20 @@ __global__ void __launch_bounds__(kThreads) rel_grad_tile_kernel(const RelGradAr
             wpv[k] = buf_f2(rWp, (int)(off * 8u));
         }
     };
-    if ((int)blockIdx.x < total) prefetch(blockIdx.x);
+    // blocks past the end of a shorter sequence add nothing and are stepped over (uniform for the workgroup)
+    auto next_block = [&](int blk) {
+        if (a.seq_len)
+            for (; blk < total; blk += gridDim.x) {
+                const int bh = blk / blocks_per_bh;
+                if (walk_pos(a.seq_len, bh, blk - bh * blocks_per_bh, blocks_per_bh) * kRgRows < seq_length(a.seq_len, bh / a.H, a.n)) break;
+            }
+        return blk;
+    };
+    int blk = next_block(blockIdx.x);
+    if (blk < total) prefetch(blk);
 
-    for (int blk = blockIdx.x; blk < total; blk += gridDim.x) {
-        const int bh = blk / blocks_per_bh, row0 = (blk - bh * blocks_per_bh) * kRgRows;
+    while (blk < total) {
+        const int bh = blk / blocks_per_bh, row0 = walk_pos(a.seq_len, bh, blk - bh * blocks_per_bh, blocks_per_bh) * kRgRows;
         const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
         // clear DS^T (hi and lo are adjacent), stage the block's Q rows and deltas
         for (int i = threadIdx.x * 8; i < 2 * nids * kRgStride; i += blockDim.x * 8)
@@ -755,7 +793,8 @@ __global__ void __launch_bounds__(kThreads) rel_grad_tile_kernel(const RelGradAr
             const int row = row0 + 16 * mc + 4 * g + m;
             dq_old[m] = row < a.n ? a.dQ[base + (int64_t)row * a.sn + 16 * fc + j] : 0.f;
         }
-        if (blk + (int)gridDim.x < total) prefetch(blk + gridDim.x);
+        const int blk_next = next_block(blk + gridDim.x);
+        if (blk_next < total) prefetch(blk_next);
         __syncthreads();
         {   // dQ of the block: wavefront -> 16 rows x 16 features
             f32x4_t dq = {0.f, 0.f, 0.f, 0.f};
@@ -788,6 +827,7 @@ __global__ void __launch_bounds__(kThreads) rel_grad_tile_kernel(const RelGradAr
             }
         }
         __syncthreads();
+        blk = blk_next;
     }
     // this workgroup's copy: [gridDim.x][nids][kD], compact-id order
     float* dst = a.drel_part + (int64_t)blockIdx.x * nids * kD;

@@ -473,6 +473,7 @@ int run_bwd_q(const bpt_graph* g, const BwdPlan& p, AttnArgs& a, hipStream_t st)
         t.num_cids = g->tiles.num_cids;
         t.nids = p.drel_part_rows;
         t.scale = a.scale;
+        t.seq_len = a.seq_len;
         if (p.drel_part_rows <= 256) {
             if (p.drel_lds > 65536)
                 BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rel_grad_tile_kernel<2>),
@@ -566,7 +567,8 @@ int run_bwd_kv_tiles(const bpt_graph* g, const BwdPlan& p, const AttnArgs& a, co
         default: break;
     }
     if (rc) return rc;
-    const int64_t zero_elems = (int64_t)a.BH * (a.N - kt.first_uncovered) * kD;
+    // threads of the zero pass of kv_tile_merge_kernel: 64 per uncovered row, or 16 per row of the graph
+    const int64_t zero_elems = a.seq_len ? (int64_t)a.BH * a.N * 16 : (int64_t)a.BH * (a.N - kt.first_uncovered) * kD;
     const int64_t blocks = (int64_t)a.BH * kt.num_multi + (zero_elems + 255) / 256;
     if (blocks > 0) {
         BPT_LAUNCH("kv_tile_merge_kernel", kv_tile_merge_kernel, dim3((unsigned)blocks), dim3(256), 0, st, t, kt.multi_tile,

@@ -752,6 +752,39 @@ int bpt_graph_transposed_to_host(const bpt_graph_t* g, int32_t* t_ptr, int32_t* 
     return copy_out(t_eid, g->t_eid, (size_t)g->num_edges);
 }
 
+int bpt_count_edges(int32_t n, int32_t k, int32_t causal, int32_t len, int64_t* edges) {
+    if (!edges || n < 2 || k < 1 || len < 0 || len > n) return BPT_ERR_INVALID_ARG;
+    if ((n & (n - 1)) != 0 || n > (1 << 22) || k > (1 << 20)) return BPT_ERR_UNSUPPORTED;
+    int levels = 1;
+    while ((1 << (levels - 1)) < n) ++levels;
+    // span rows: on every level above the tokens the kept nodes hold each token once
+    int64_t total = (int64_t)len * (levels - 1);
+    for (int64_t i = 0; i < len; ++i) {
+        int64_t d = 1;   // self
+        for (int64_t q = i - 1; q >= 0;) {   // left side: everything left of a token is kept
+            int64_t e = std::max<int64_t>(q - k + 1, 0);
+            if (e & 1) e -= 1;
+            d += q - e + 1;
+            q = e >= 1 ? (e - 1) >> 1 : -1;
+        }
+        if (!causal) {
+            int64_t p = i + 1;
+            for (int l = 0;; ++l) {   // right side: level l keeps ceil(len / 2^l) nodes
+                const int64_t cnt = (len + ((int64_t)1 << l) - 1) >> l;
+                if (p >= cnt) break;
+                int64_t e = std::min<int64_t>(p + k - 1, cnt - 1);
+                if (!(e & 1) && e + 1 < cnt) e += 1;
+                d += e - p + 1;
+                if (e + 1 >= cnt) break;
+                p = (e + 1) >> 1;
+            }
+        }
+        total += d;
+    }
+    *edges = total;
+    return BPT_OK;
+}
+
 const char* bpt_strerror(int status) {
     switch (status) {
         case BPT_OK: return "ok";

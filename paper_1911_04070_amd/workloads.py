@@ -34,6 +34,7 @@ class Workload:
     D: int
     dtype: str          # "f32" or "bf16": storage type of Q,K,V,Rel,dO,out
     backward: bool
+    length_mix: str = ""  # "" = every sequence has n tokens; else the recipe of make_lengths
 
     @property
     def num_nodes(self) -> int:
@@ -60,6 +61,25 @@ WORKLOADS: Dict[str, Workload] = {
 }
 for _k in (2, 4, 8, 16, 32):
     WORKLOADS["ksweep%d" % _k] = Workload("ksweep%d" % _k, 5, 4096, _k, False, 8, 8, 64, "bf16", True)
+
+
+# the sentence-classification batch with sentences of different lengths padded to n (the text
+# corpora of Sec. 4.1 hold sentences and reviews of very different lengths)
+WORKLOADS["cls_lengths"] = replace(WORKLOADS["cls"], name="cls_lengths", index=6, length_mix="reviews")
+WORKLOADS["lm_lengths"] = replace(WORKLOADS["lm"], name="lm_lengths", index=7, B=8, length_mix="reviews")
+
+
+def make_lengths(w: Workload) -> np.ndarray:
+    """Token counts of the B sequences of a workload, int32.  "reviews": log-normal lengths with
+    median 0.4 n and sigma 0.6, clipped to [8, n] -- a long-tailed mix like that of review
+    and sentence corpora, where a batch padded to its longest member is about half padding."""
+    if not w.length_mix:
+        return np.full(w.B, w.n, dtype=np.int32)
+    if w.length_mix != "reviews":
+        raise ValueError("unknown length mix %r" % (w.length_mix,))
+    rng = np.random.Generator(np.random.PCG64(SEED_BASE + 1000 * w.index + 77))
+    x = np.exp(rng.normal(np.log(0.4 * w.n), 0.6, size=w.B))
+    return np.clip(np.rint(x), 8, w.n).astype(np.int32)
 
 
 def shrink(w: Workload, **kw) -> Workload:

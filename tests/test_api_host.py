@@ -6,6 +6,8 @@ import re
 
 import pytest
 
+import oracle
+
 from paper_1911_04070_amd import binding as bpt
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -90,3 +92,18 @@ def test_product_package_does_not_import_the_oracle():
                 text = open(os.path.join(dirpath, f)).read()
                 assert "import oracle" not in text and "from oracle" not in text, f
                 assert "bpt_oracle" not in text, f
+
+
+def test_edge_count_of_shorter_sequences_matches_the_oracle():
+    # host arithmetic of the library (no device involved) against the oracle's builder
+    for n, k, causal in ((2, 1, False), (8, 1, True), (16, 2, False), (32, 3, False), (64, 40, True), (256, 4, False),
+                         (512, 4, False), (1024, 7, True)):
+        lengths = range(1, n + 1) if n <= 64 else (1, 2, 3, n // 3, n // 2 - 1, n // 2, n // 2 + 1, n - 1, n)
+        for length in lengths:
+            want = oracle.build_graph_len(n, length, k, causal).num_edges
+            assert bpt.bpt_count_edges(n, k, causal, length) == want, (n, k, causal, length)
+        assert bpt.bpt_count_edges(n, k, causal, 0) == 0
+    with pytest.raises(bpt.BptError):
+        bpt.bpt_count_edges(64, 2, False, 65)
+    with pytest.raises(bpt.BptError):
+        bpt.bpt_count_edges(48, 2, False, 5)

@@ -250,8 +250,11 @@ def test_lengths_equal_to_n_change_nothing():
     b = bpt.bpt_attn_fwd(g, Q, K, V, R, scale=w.scale, seq_len=lens_d)
     ga = bpt.bpt_attn_bwd(g, Q, K, V, R, a[1], dO, scale=w.scale)
     gb = bpt.bpt_attn_bwd(g, Q, K, V, R, b[1], dO, scale=w.scale, seq_len=lens_d)
-    for s, t in zip(a + tuple(ga), b + tuple(gb)):
+    for s, t in zip(a + tuple(ga[:3]), b + tuple(gb[:3])):
         assert torch.equal(s, t)
+    # d_rel is a sum over the whole batch; with seq_len the work is spread over the workgroups in
+    # another order, so its partial sums round differently
+    assert float((ga[3] - gb[3]).abs().max()) <= 1e-3 * float(ga[3].abs().max())
     g.destroy()
 
 
