@@ -19,7 +19,8 @@ namespace {
 // query come from the query side (`stat`), so dS is formed in fp32 before it is
 // rounded to bf16 for the product.  No atomics: a tile whose query list is cut into
 // several tasks is summed by kv_tile_merge_kernel in task order.
-constexpr int kMaxBiasChunks = 6;
+constexpr int kMaxBiasChunks = 10;   // 16-id chunks of the table a key tile can meet (W + levels - 1 ids <= 160)
+constexpr int kRegBiasChunks = 6;    // of which this many are register operands; the others are parked in LDS
 struct KeyArgs {
     const bf16_t *Q, *K, *V, *rel, *dout;
     const float2* stat;
@@ -51,6 +52,11 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyA
     float2* stat_s = reinterpret_cast<float2*>(smem + (size_t)kTileWaves * (32 * bstride * sizeof(float) +
                                                                             64 * kRowStride * sizeof(bf16_t))) +
                      (size_t)wave * 32;                                                          // [32 queries] (lse, delta)
+    // table operands beyond the kRegBiasChunks kept in registers: every lane parks and re-reads its own 32 bytes
+    constexpr int kParked = NBC > kRegBiasChunks ? NBC - kRegBiasChunks : 0;
+    uint4* rb_s = reinterpret_cast<uint4*>(smem + (size_t)kTileWaves * (32 * bstride * sizeof(float) +
+                                                                        64 * kRowStride * sizeof(bf16_t) + 32 * sizeof(float2))) +
+                  ((size_t)wave * (kParked > 0 ? kParked : 1) * 64 + lane) * 2;
     const float qscale = a.scale * kLog2e;
     const int groups = (a.num_tasks + kTileWaves - 1) / kTileWaves;
     const rsrc_t rC = make_rsrc(a.cols, (uint32_t)a.num_chunks * 64u);    // [chunks][16] int32
@@ -117,7 +123,8 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyA
         const bf16x8_t kb1 = *reinterpret_cast<const bf16x8_t*>(a.K + krow + 8);
         const bf16x8_t vb0 = *reinterpret_cast<const bf16x8_t*>(a.V + krow);
         const bf16x8_t vb1 = *reinterpret_cast<const bf16x8_t*>(a.V + krow + 8);
-        bf16x8_t rb[NBC][2];
+        constexpr int kInRegs = NBC < kRegBiasChunks ? NBC : kRegBiasChunks;
+        bf16x8_t rb[kInRegs][2];
 #pragma unroll
         for (int bc = 0; bc < NBC; ++bc) {
             const int bid = 16 * bc + j;
@@ -127,8 +134,13 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyA
             else if (bid - a.W + 1 < a.num_levels)
                 row = (bid - a.W + 1) * a.W + a.zero;            // r_anc of the ancestor's level
             const bf16_t* rr = a.rel + (int64_t)row * kD + 16 * g;
-            rb[bc][0] = *reinterpret_cast<const bf16x8_t*>(rr);
-            rb[bc][1] = *reinterpret_cast<const bf16x8_t*>(rr + 8);
+            if (bc < kInRegs) {
+                rb[bc][0] = *reinterpret_cast<const bf16x8_t*>(rr);
+                rb[bc][1] = *reinterpret_cast<const bf16x8_t*>(rr + 8);
+            } else {
+                rb_s[(bc - kInRegs) * 128] = *reinterpret_cast<const uint4*>(rr);
+                rb_s[(bc - kInRegs) * 128 + 1] = *reinterpret_cast<const uint4*>(rr + 8);
+            }
         }
         load_rows();     // pair 0 (waits for its ids)
         uint2 mp[2] = {mpn[0], mpn[1]};
@@ -173,8 +185,16 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyA
 #pragma unroll
                 for (int bc = 0; bc < NBC; ++bc) {
                     f32x4_t b4 = {0.f, 0.f, 0.f, 0.f};
-                    b4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(q0, rb[bc][0], b4, 0, 0, 0);
-                    b4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(q1, rb[bc][1], b4, 0, 0, 0);
+                    bf16x8_t r0, r1;
+                    if (bc < kInRegs) {
+                        r0 = rb[bc][0];
+                        r1 = rb[bc][1];
+                    } else {
+                        r0 = __builtin_bit_cast(bf16x8_t, rb_s[(bc - kInRegs) * 128]);
+                        r1 = __builtin_bit_cast(bf16x8_t, rb_s[(bc - kInRegs) * 128 + 1]);
+                    }
+                    b4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(q0, r0, b4, 0, 0, 0);
+                    b4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(q1, r1, b4, 0, 0, 0);
 #pragma unroll
                     for (int r = 0; r < 4; ++r) bias_s[(16 * ci + 4 * g + r) * bstride + 16 * bc + j] = b4[r];
                 }

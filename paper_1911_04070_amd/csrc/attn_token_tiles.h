@@ -674,12 +674,18 @@ __device__ __forceinline__ bf16x8_t lds_tr8(const bf16_t* base, int stride, int 
     return __builtin_bit_cast(bf16x8_t, xy);
 }
 
-constexpr int kRgPrefetch = 8;   // tile slots per thread fetched one block ahead (512 threads: 16 chunks)
+// tile slots per thread fetched one block ahead: 8 (512 threads: 16 chunks) with up to 256 ids, 24 with more --
+// those graphs have 25..30 slots per thread and block, and one workgroup per compute unit to hide their latency
+template <int CPW>
+struct RgPrefetch {
+    static constexpr int value = CPW == 2 ? 8 : 32;
+};
 constexpr int kRgTileMaxIds = 512;
 // CPW: 16-id chunks per wavefront (2: up to 256 ids, 4: up to 512)
 template <int CPW>
 __global__ void __launch_bounds__(kThreads, CPW == 2 ? 4 : 2) rel_grad_tile_kernel(const RelGradArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
+    constexpr int kRgPrefetch = RgPrefetch<CPW>::value;
     const int nids = a.nids;
     bf16_t* ds_hi = reinterpret_cast<bf16_t*>(smem);                 // [nids][kRgStride]: DS^T, rows of the block along a line
     bf16_t* ds_lo = ds_hi + nids * kRgStride;
@@ -734,6 +740,7 @@ __global__ void __launch_bounds__(kThreads, CPW == 2 ? 4 : 2) rel_grad_tile_kern
         const rsrc_t rWp = make_rsrc(a.wp + (int64_t)bh * a.num_chunks * 256, (uint32_t)a.num_chunks * 2048u);
 #pragma unroll
         for (int k = 0; k < kRgPrefetch; ++k) {
+            if (k >= 8 && s_begin + k * kThreads >= s_end) break;   // uniform: no slot of the block is that far
             const int sl = s_begin + (int)threadIdx.x + k * kThreads;
             const uint32_t off = sl < s_end ? (uint32_t)sl : 0x1FFFFFFFu;   // past the block: an offset outside the buffers
             code[k] = (int)(short)__builtin_amdgcn_raw_buffer_load_b16(rMap, (int)(off * 2u), 0, 0);

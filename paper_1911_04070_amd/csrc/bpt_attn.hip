@@ -363,8 +363,9 @@ int plan_bwd(const bpt_graph* g, const bpt_shape_t* s, BwdPlan* p) {
             p->drel_lds = rg_lds;
         }
         if (g->ktiles.num_tasks > 0 && g->ktiles.nb_pad <= 16 * kMaxBiasChunks) {
+            const int parked = std::max(0, g->ktiles.nb_pad / 16 - kRegBiasChunks);   // table operands kept in LDS
             p->kv_lds = (size_t)kTileWaves * (32 * (g->ktiles.nb_pad + 1) * sizeof(float) + 64 * kRowStride * sizeof(bf16_t) +
-                                              32 * sizeof(float2));
+                                              32 * sizeof(float2) + (size_t)parked * 64 * 32);
             p->kv_tiles = p->kv_lds <= lim.lds;
         }
         p->drel_grid_y = p->drel_tile ? 1 : (p->drel_rows + kRgIds - 1) / kRgIds;
@@ -564,6 +565,10 @@ int run_bwd_kv_tiles(const bpt_graph* g, const BwdPlan& p, const AttnArgs& a, co
         case 4: rc = launch_kv_tiles<4>(t, p, lim, st); break;
         case 5: rc = launch_kv_tiles<5>(t, p, lim, st); break;
         case 6: rc = launch_kv_tiles<6>(t, p, lim, st); break;
+        case 7: rc = launch_kv_tiles<7>(t, p, lim, st); break;
+        case 8: rc = launch_kv_tiles<8>(t, p, lim, st); break;
+        case 9: rc = launch_kv_tiles<9>(t, p, lim, st); break;
+        case 10: rc = launch_kv_tiles<10>(t, p, lim, st); break;
         default: break;
     }
     if (rc) return rc;

@@ -160,6 +160,13 @@ def test_rows_cut_into_several_segments():
     run_case(w)
 
 
+@pytest.mark.parametrize("n,k,causal", [(4096, 64, True), (1024, 72, False), (2048, 50, False)])
+def test_large_density_on_key_tiles(n, k, causal):
+    # the paper's character-level density k = 64 (Sec. 4.2) and the largest the key tiles take:
+    # 7..10 chunks of 16 relative-position ids per level, the last ones parked in LDS
+    run_case(Workload("dense_k", 11, n, k, causal, 1, 2, 64, "bf16", True))
+
+
 FULL = ["cls", "lm", "xl", "ksweep2", "ksweep4", "ksweep8", "ksweep16", "ksweep32"]
 
 
