@@ -27,16 +27,16 @@ HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
 # workload; the runs and their commands are in profiles/.  None where not measured.
 MEASURED_TRAFFIC = {
     "lm": {  # profiles/lm_n8192_k8_causal_bf16_kernels.md
-        "bwd_kv_tile_kernel": int((305324.3 * 2.0 + 278804.1) * 1024),
-        "bwd_q_tile_kernel": int((144328.6 * 2.0 + 309302.1) * 1024),
-        "rel_grad_tile_kernel": int((173235.0 * 2.0 + 90112.5) * 1024),
-        "fwd_tile_kernel": int((116797.8 * 2.0 + 33859.6) * 1024),
-        "bwd_q_span_tile_kernel": int((67573.0 * 2.0 + 99728.0) * 1024),
-        "fwd_span_tile_kernel": int((49572.7 * 2.0 + 49974.2) * 1024),
+        "bwd_kv_tile_kernel": int((311688.7 * 2.0 + 278797.4) * 1024),
+        "bwd_q_tile_kernel": int((144535.4 * 2.0 + 309288.4) * 1024),
+        "rel_grad_tile_kernel": int((173310.2 * 2.0 + 90112.8) * 1024),
+        "fwd_tile_kernel": int((117098.8 * 2.0 + 33873.4) * 1024),
+        "bwd_q_span_tile_kernel": int((67584.0 * 2.0 + 99544.1) * 1024),
+        "fwd_span_tile_kernel": int((49585.8 * 2.0 + 49983.9) * 1024),
     },
 }
 # HBM bytes of one whole step (all kernels, same counters and scaling)
-MEASURED_STEP_TRAFFIC = {"lm": 2749650841}
+MEASURED_STEP_TRAFFIC = {"lm": 2763413708}
 
 
 def parse():
