@@ -319,17 +319,32 @@ __global__ void __launch_bounds__(256) kv_tile_merge_kernel(const KeyArgs a, con
     // a tile none of whose keys exists in this (shorter) sequence has no partial sums: zeros
     const int len = seq_length(a.seq_len, bh / a.H, a.n);
     const bool gone = ((len + (1 << level) - 1) >> level) - (node0 - (2 * a.n - ((2 * a.n) >> level))) <= 0;
-    for (int i = threadIdx.x; i < nkeys * kD; i += blockDim.x) {
-        const int key = i >> 6, f = i & 63;
-        float sk = 0.f, sv = 0.f;
-        for (int p = gone ? multi_ptr[mt + 1] : multi_ptr[mt]; p < multi_ptr[mt + 1]; ++p) {
-            const float* src = a.part + (((int64_t)bh * a.num_part + p) * 16 + key) * (2 * kD) + f;
-            sk += src[0];
-            sv += src[kD];
+    // thread -> (key, 4 consecutive values of its 64 dK | 64 dV); four partial sums in flight, combined in a fixed order
+    const int p0 = gone ? multi_ptr[mt + 1] : multi_ptr[mt], p1 = multi_ptr[mt + 1];
+    for (int i = threadIdx.x; i < nkeys * 32; i += blockDim.x) {
+        const int key = i >> 5, q4 = (i & 31) * 4;
+        const float* src = a.part + (((int64_t)bh * a.num_part) * 16 + key) * (2 * kD) + q4;
+        const int64_t pstride = (int64_t)16 * 2 * kD;
+        float4 s0 = make_float4(0.f, 0.f, 0.f, 0.f), s1 = s0, s2 = s0, s3 = s0;
+        int p = p0;
+        for (; p + 3 < p1; p += 4) {
+            const float4 x0 = *reinterpret_cast<const float4*>(src + p * pstride);
+            const float4 x1 = *reinterpret_cast<const float4*>(src + (p + 1) * pstride);
+            const float4 x2 = *reinterpret_cast<const float4*>(src + (p + 2) * pstride);
+            const float4 x3 = *reinterpret_cast<const float4*>(src + (p + 3) * pstride);
+            s0.x += x0.x; s0.y += x0.y; s0.z += x0.z; s0.w += x0.w;
+            s1.x += x1.x; s1.y += x1.y; s1.z += x1.z; s1.w += x1.w;
+            s2.x += x2.x; s2.y += x2.y; s2.z += x2.z; s2.w += x2.w;
+            s3.x += x3.x; s3.y += x3.y; s3.z += x3.z; s3.w += x3.w;
         }
-        const int64_t at = base + (int64_t)(node0 + key) * a.sn + f;
-        a.dK[at] = sk;
-        a.dV[at] = sv;
+        for (; p < p1; ++p) {
+            const float4 x0 = *reinterpret_cast<const float4*>(src + p * pstride);
+            s0.x += x0.x; s0.y += x0.y; s0.z += x0.z; s0.w += x0.w;
+        }
+        const float4 t = make_float4((s0.x + s1.x) + (s2.x + s3.x), (s0.y + s1.y) + (s2.y + s3.y),
+                                     (s0.z + s1.z) + (s2.z + s3.z), (s0.w + s1.w) + (s2.w + s3.w));
+        float* dst = (q4 < kD ? a.dK + q4 : a.dV + (q4 - kD)) + base + (int64_t)(node0 + key) * a.sn;
+        *reinterpret_cast<float4*>(dst) = t;
     }
 }
 
@@ -363,20 +378,20 @@ __global__ void __launch_bounds__(1024) drel_reduce_kernel(const float* __restri
     __shared__ float s[16][kD];
     const int row = blockIdx.x, lane = threadIdx.x & 63, grp = threadIdx.x >> 6;
     const int prow = id_to_cid ? id_to_cid[row] : row;
-    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f, a4 = 0.f, a5 = 0.f, a6 = 0.f, a7 = 0.f;
     if (prow >= 0 && prow < covered_rows) {
         const float* src = parts + (int64_t)prow * kD + lane;
         const int64_t stride = (int64_t)covered_rows * kD;
         int p = grp;
-        for (; p + 48 < num_parts; p += 64) {
-            a0 += src[p * stride];
-            a1 += src[(p + 16) * stride];
-            a2 += src[(p + 32) * stride];
-            a3 += src[(p + 48) * stride];
+        for (; p + 112 < num_parts; p += 128) {   // eight loads in flight per round trip
+            const float x0 = src[p * stride], x1 = src[(p + 16) * stride], x2 = src[(p + 32) * stride];
+            const float x3 = src[(p + 48) * stride], x4 = src[(p + 64) * stride], x5 = src[(p + 80) * stride];
+            const float x6 = src[(p + 96) * stride], x7 = src[(p + 112) * stride];
+            a0 += x0; a1 += x1; a2 += x2; a3 += x3; a4 += x4; a5 += x5; a6 += x6; a7 += x7;
         }
         for (; p < num_parts; p += 16) a0 += src[p * stride];
     }
-    s[grp][lane] = (a0 + a1) + (a2 + a3);
+    s[grp][lane] = ((a0 + a1) + (a2 + a3)) + ((a4 + a5) + (a6 + a7));
     __syncthreads();
     for (int w = 8; w > 0; w >>= 1) {
         if (grp < w) s[grp][lane] += s[grp + w][lane];

@@ -368,7 +368,7 @@ __global__ void __launch_bounds__(kSpanBigThreads) fwd_span_merge_kernel(const S
 // and dS = w - delta p are final and dQ = scale * dS K_block (r_anc drops out: the dS of a row
 // sum to zero).  An ancestor stores the partial sums A = W K, Bv = P K, delta, which the merge
 // kernel turns into dQ = scale * (sum A - delta * sum Bv).
-__global__ void __launch_bounds__(kTileThreads) bwd_q_span_tile_kernel(const SpanArgs a) {
+__global__ void __launch_bounds__(kTileThreads, 3) bwd_q_span_tile_kernel(const SpanArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
