@@ -75,57 +75,26 @@ __device__ __forceinline__ float span_shift(const SpanArgs& a, int level, int g,
 // A block of 32 tokens past the end of a shorter sequence: nothing is read; its spans inside the
 // block get zero rows (forward: out, lse; backward: dQ, and a `stat` entry that switches the row
 // off on the key side) and its ancestors an empty partial (forward: no weight; backward: zero sums).
+// The spans of a level are consecutive nodes, so the rows are written 16 bytes per lane.
 __device__ __forceinline__ void span_block_gone(const SpanArgs& a, int bh, int blk, int t0, int nblk, int nanc,
-                                                int ngroups, int64_t base, bool forward, int g, int j) {
-    for (int grp = 0; grp < ngroups; ++grp) {
-        int level, loc;
-        bool valid;
-        span_slot(grp, j, a.L, level, loc, valid);
-        const int node = span_level_offset(a.n, level) + (t0 >> level) + loc;
-        if (grp < 2) {
-            if (g == 0 && valid) {
-                if (forward)
-                    a.lse[(int64_t)bh * a.N + node] = 0.f;
-                else
-                    a.stat[(int64_t)bh * a.N + node] = make_float2(kLseGone, 0.f);
-            }
-            for (int r = 0; r < 4; ++r) {
-                const int slot = 4 * g + r;
-                if (grp == 1 && slot == 15) continue;
-                int lv2, loc2;
-                bool ok2;
-                span_slot(grp, slot, a.L, lv2, loc2, ok2);
-                if (!ok2) continue;
-                const int64_t at = base + (int64_t)span_slot_node(grp, slot, a.L, a.n, t0) * a.sn + j;
-                for (int f = 0; f < 4; ++f) {
-                    if (forward)
-                        a.out[at + 16 * f] = 0;
-                    else
-                        a.dQ[at + 16 * f] = 0.f;
-                }
-            }
+                                                int64_t base, bool forward, int lane) {
+    const int top = min(kSpanInLevels, a.L);
+    for (int level = 1; level <= top; ++level) {
+        const int node0 = span_level_offset(a.n, level) + (t0 >> level), cnt = kSpanTok >> level;
+        if (forward) {
+            for (int i = lane; i < cnt * 8; i += 64)     // 64 bf16 per row
+                *reinterpret_cast<uint4*>(a.out + base + (int64_t)(node0 + (i >> 3)) * a.sn + (i & 7) * 8) = make_uint4(0u, 0u, 0u, 0u);
+            if (lane < cnt) a.lse[(int64_t)bh * a.N + node0 + lane] = 0.f;
         } else {
-            const int stride = forward ? kPartStride : kQPartStride;
-            if (g == 0 && valid) {
-                float* dst = a.part + (((int64_t)bh * nanc + j) * nblk + blk) * stride;
-                if (forward) {
-                    dst[64] = kNegBig;
-                    dst[65] = 0.f;
-                } else {
-                    dst[2 * kD] = 0.f;
-                }
-            }
-            for (int r = 0; r < 4; ++r) {
-                const int slot = 4 * g + r;
-                if (slot < nanc) {
-                    float* dst = a.part + (((int64_t)bh * nanc + slot) * nblk + blk) * stride + j;
-                    for (int f = 0; f < 4; ++f) {
-                        dst[16 * f] = 0.f;
-                        if (!forward) dst[kD + 16 * f] = 0.f;
-                    }
-                }
-            }
+            for (int i = lane; i < cnt * 16; i += 64)    // 64 floats per row
+                *reinterpret_cast<float4*>(a.dQ + base + (int64_t)(node0 + (i >> 4)) * a.sn + (i & 15) * 4) = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (lane < cnt) a.stat[(int64_t)bh * a.N + node0 + lane] = make_float2(kLseGone, 0.f);
         }
+    }
+    const int stride = forward ? kPartStride : kQPartStride;   // 66: sums, max, weight; 132: A, Bv, delta, padding
+    for (int slot = 0; slot < nanc; ++slot) {
+        float* dst = a.part + (((int64_t)bh * nanc + slot) * nblk + blk) * stride;
+        for (int i = lane; i < stride; i += 64) dst[i] = forward && i == 64 ? kNegBig : 0.f;
     }
 }
 
@@ -147,7 +116,7 @@ __global__ void __launch_bounds__(kTileThreads) fwd_span_tile_kernel(const SpanA
 
     // the block's K rows as A operands (token j of chunk c, features 16g..16g+15); V rows into LDS
     if (t0 >= len) {   // wave-uniform: a block past the end of a shorter sequence
-        span_block_gone(a, bh, blk, t0, nblk, nanc, ngroups, base, true, g, j);
+        span_block_gone(a, bh, blk, t0, nblk, nanc, base, true, lane);
         return;
     }
     bf16x8_t ka[2][2];
@@ -385,7 +354,7 @@ __global__ void __launch_bounds__(kTileThreads, 3) bwd_q_span_tile_kernel(const 
     const int len = seq_length(a.seq_len, bh / a.H, a.n);
 
     if (t0 >= len) {   // wave-uniform: a block past the end of a shorter sequence
-        span_block_gone(a, bh, blk, t0, nblk, nanc, ngroups, base, false, g, j);
+        span_block_gone(a, bh, blk, t0, nblk, nanc, base, false, lane);
         return;
     }
     bf16x8_t ka[2][2], va[2][2];

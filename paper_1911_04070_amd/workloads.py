@@ -66,6 +66,8 @@ for _k in (2, 4, 8, 16, 32):
 # the sentence-classification batch with sentences of different lengths padded to n (the text
 # corpora of Sec. 4.1 hold sentences and reviews of very different lengths)
 WORKLOADS["cls_lengths"] = replace(WORKLOADS["cls"], name="cls_lengths", index=6, length_mix="reviews")
+# forward only, as in the paper's inference throughput comparison (Sec. 4.4)
+WORKLOADS["lm_infer"] = replace(WORKLOADS["lm"], name="lm_infer", backward=False)
 WORKLOADS["lm_lengths"] = replace(WORKLOADS["lm"], name="lm_lengths", index=7, B=8, length_mix="reviews")
 
 

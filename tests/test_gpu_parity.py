@@ -247,6 +247,28 @@ def test_sequences_of_different_lengths(dtype, n, k, causal, H, lengths):
     run_lengths_case(w, lengths)
 
 
+def test_lengths_with_node_major_memory_and_many_ids():
+    # [B,N,H,D] memory through the strides, and a density whose key tiles park table operands in LDS
+    w = Workload("lengths_dense", 23, 1024, 64, False, 2, 2, 64, "bf16", True)
+    lengths = [700, 1024]
+    x = make_inputs(w)
+    g = bpt.bpt_build_graph(w.n, w.k, w.causal)
+    dev = {}
+    for key in ("Q", "K", "V", "dO"):
+        dev[key] = to_dev(x[key], w.dtype).permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    R = to_dev(x["Rel"], w.dtype)
+    lens_d = torch.tensor(lengths, dtype=torch.int32, device="cuda")
+    out_d, lse_d = bpt.bpt_attn_fwd(g, dev["Q"], dev["K"], dev["V"], R, scale=w.scale, seq_len=lens_d)
+    grads = bpt.bpt_attn_bwd(g, dev["Q"], dev["K"], dev["V"], R, lse_d, dev["dO"], scale=w.scale, seq_len=lens_d)
+    torch.cuda.synchronize()
+    o, l, _ = oracle.attn_fwd_lengths(w.n, w.k, w.causal, lengths, x["Q"], x["K"], x["V"], x["Rel"], w.scale)
+    refs = oracle.attn_bwd_lengths(w.n, w.k, w.causal, lengths, x["Q"], x["K"], x["V"], x["Rel"], x["dO"], w.scale)
+    for name, got_t, ref in zip(("out", "lse", "dQ", "dK", "dV", "d_rel"), (out_d, lse_d) + tuple(grads), (o, l) + refs):
+        err = float(np.abs(host(got_t) - ref).max())
+        assert err <= TOL[w.dtype], (name, err)
+    g.destroy()
+
+
 def test_lengths_equal_to_n_change_nothing():
     w = Workload("full_lengths", 22, 1024, 4, False, 2, 2, 64, "bf16", True)
     x = make_inputs(w)
