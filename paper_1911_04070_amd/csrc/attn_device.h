@@ -46,11 +46,26 @@ struct AttnArgs {
     int32_t lg;             // log2(n_tokens)
 };
 
+// ---- wave-uniform loads of read-only tables -------------------------------------------
+// Graph metadata and sequence lengths are written by no attention kernel, and the tile kernels
+// read them at addresses that are the same in all lanes.  Read as scalar loads from the constant
+// address space they stay out of the vector-memory queue: vector loads return in order, so a
+// wait for such a value issued as a vector load would also wait for every row fetch in flight
+// (which is what a software-pipelined loop must not do at each tile boundary).
+typedef const int32_t __attribute__((address_space(4))) * const_i32_ptr;
+__device__ __forceinline__ int uniform_i32(const int32_t* p, int idx) {
+    return reinterpret_cast<const_i32_ptr>(reinterpret_cast<uintptr_t>(p))[__builtin_amdgcn_readfirstlane(idx)];
+}
+
 // ---- sequences shorter than n ------------------------------------------------------
 // A batch entry with len < n tokens keeps the nodes whose first token exists; an edge counts
 // iff both of its nodes are kept.  Rows of nodes that are not kept produce zeros.
 __device__ __forceinline__ int seq_length(const int32_t* seq_len, int b, int n) {
     return seq_len ? min(max(seq_len[b], 0), n) : n;
+}
+// the same for a wave-uniform batch index
+__device__ __forceinline__ int seq_length_u(const int32_t* seq_len, int b, int n) {
+    return seq_len ? min(max(uniform_i32(seq_len, b), 0), n) : n;
 }
 // first token of a node of the tree over n = 2^lg tokens (ids are level-major)
 __device__ __forceinline__ int node_first_token(int id, int lg) {

@@ -20,6 +20,7 @@ namespace {
 // rounded to bf16 for the product.  No atomics: a tile whose query list is cut into
 // several tasks is summed by kv_tile_merge_kernel in task order.
 constexpr int kMaxBiasChunks = 10;   // 16-id chunks of the table a key tile can meet (W + levels - 1 ids <= 160)
+constexpr int kKvOutStride = 2 * kD + 4;   // floats per key row of the output staging in LDS (528 bytes)
 constexpr int kRegBiasChunks = 6;    // of which this many are register operands; the others are parked in LDS
 struct KeyArgs {
     const bf16_t *Q, *K, *V, *rel, *dout;
@@ -67,15 +68,15 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyA
         const int bh = walk_bh(a.seq_len, slab, a.BH, a.H);
         const int task = walk_pos(a.seq_len, slab, w.t - slab * groups, groups) * kTileWaves + wave;
         if (task >= a.num_tasks) continue;
-        const int kt = a.task_tile[task], c0 = a.task_c0[task], part = a.task_part[task];
-        const int node0 = a.tile_node0[kt], info = a.tile_info[kt];
+        const int kt = uniform_i32(a.task_tile, task), c0 = uniform_i32(a.task_c0, task), part = uniform_i32(a.task_part, task);
+        const int node0 = uniform_i32(a.tile_node0, kt), info = uniform_i32(a.tile_info, kt);
         const int level = info & 255, nkeys = info >> 8;
         // a shorter sequence keeps the first ceil(len / 2^level) nodes of the level; queries that are
         // not kept carry kLseGone in `stat`
-        const int len = seq_length(a.seq_len, bh / a.H, a.n);
+        const int len = seq_length_u(a.seq_len, bh / a.H, a.n);
         const int kept_keys = ((len + (1 << level) - 1) >> level) - (node0 - (2 * a.n - ((2 * a.n) >> level)));
         const bool key_kept = j < kept_keys;
-        const int nch = a.task_nch[task];
+        const int nch = uniform_i32(a.task_nch, task);
         const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
         // wave-uniform: no key of the tile exists in this sequence; kv_tile_merge_kernel writes the zero rows
         if (kept_keys <= 0) continue;
@@ -256,26 +257,30 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyA
                 dv[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pL, gB, dv[f], 0, 0, 0);
             }
         }
-        // C[m = key][n = feature]: lane holds keys 4g..4g+3, feature 16f + j
+        // C[m = key][n = feature]: lane holds keys 4g..4g+3, feature 16f + j.  Stored from there, a
+        // wavefront instruction would write 4-byte pieces of 4 rows; the sums go through LDS (the
+        // row buffers are free now) and leave as 16 bytes per lane, rows of 512 contiguous bytes.
+        wave_lds_sync();   // the last pair's reads of q_s, g_s are done
+        float* o_s = reinterpret_cast<float*>(q_s);   // [16 keys][kKvOutStride]: 64 dK | 64 dV
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int key = 4 * g + r;
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int f = 0; f < 4; ++f) {
+                o_s[(4 * g + r) * kKvOutStride + 16 * f + j] = a.scale * dk[f][r];
+                o_s[(4 * g + r) * kKvOutStride + kD + 16 * f + j] = dv[f][r];
+            }
+        wave_lds_sync();
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int idx = lane + 64 * i, key = idx >> 5, q4 = (idx & 31) * 4;
             if (key < nkeys) {
-                if (part < 0) {
-                    const int64_t at = base + (int64_t)(node0 + key) * a.sn + j;
-#pragma unroll
-                    for (int f = 0; f < 4; ++f) {
-                        a.dK[at + 16 * f] = a.scale * dk[f][r];
-                        a.dV[at + 16 * f] = dv[f][r];
-                    }
-                } else {
-                    float* dst = a.part + (((int64_t)bh * a.num_part + part) * 16 + key) * (2 * kD) + j;
-#pragma unroll
-                    for (int f = 0; f < 4; ++f) {
-                        dst[16 * f] = a.scale * dk[f][r];
-                        dst[kD + 16 * f] = dv[f][r];
-                    }
-                }
+                const float4 v = *reinterpret_cast<const float4*>(o_s + key * kKvOutStride + q4);
+                float* dst;
+                if (part < 0)
+                    dst = (q4 < kD ? a.dK + q4 : a.dV + (q4 - kD)) + base + (int64_t)(node0 + key) * a.sn;
+                else
+                    dst = a.part + (((int64_t)bh * a.num_part + part) * 16 + key) * (2 * kD) + q4;
+                *reinterpret_cast<float4*>(dst) = v;
             }
         }
         wave_lds_sync();

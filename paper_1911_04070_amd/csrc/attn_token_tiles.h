@@ -165,7 +165,7 @@ __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArg
             c.bh = walk_bh(a.seq_len, slab, a.BH, a.H);
             c.tile = walk_pos(a.seq_len, slab, c.t - slab * groups_per_bh, groups_per_bh) * kTileWaves + wave;
             if (c.tile >= a.num_tiles) continue;
-            if (a.seq_len && c.tile * 16 >= seq_length(a.seq_len, c.bh / a.H, a.n)) {
+            if (a.seq_len && c.tile * 16 >= seq_length_u(a.seq_len, c.bh / a.H, a.n)) {
                 const int64_t base = (int64_t)(c.bh / a.H) * a.sb + (int64_t)(c.bh % a.H) * a.sh;
                 bf16_t* orow = a.out + base + (int64_t)(c.tile * 16 + r8) * a.sn + piece * 8;
                 *reinterpret_cast<uint4*>(orow) = make_uint4(0u, 0u, 0u, 0u);
@@ -261,7 +261,7 @@ __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArg
             }
             if (a.seq_len) {   // uniform
                 wave_lds_sync();
-                mask_bias(a, bias_s, cc.tile * 16, seq_length(a.seq_len, cc.bh / a.H, a.n), g, j);
+                mask_bias(a, bias_s, cc.tile * 16, seq_length_u(a.seq_len, cc.bh / a.H, a.n), g, j);
             }
         }
         wave_lds_sync();  // the previous pair's reads of k_s, v_s (and the previous tile's of bias_s) are done
@@ -352,7 +352,7 @@ __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArg
         if (cc.pair == cc.npairs - 1) {   // the tile is complete
             const int64_t base = (int64_t)(cc.bh / a.H) * a.sb + (int64_t)(cc.bh % a.H) * a.sh;
             const int t0 = cc.tile * 16;
-            const int len = seq_length(a.seq_len, cc.bh / a.H, a.n);   // tokens past the end give zeros
+            const int len = seq_length_u(a.seq_len, cc.bh / a.H, a.n);   // tokens past the end give zeros
             // row sums: token j is spread over the 4 lane groups
             float l = l_part + __shfl_xor(l_part, 16);
             l += __shfl_xor(l, 32);
@@ -426,7 +426,7 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_q_tile_kernel(const TileA
             c.bh = walk_bh(a.seq_len, slab, a.BH, a.H);
             c.tile = walk_pos(a.seq_len, slab, c.t - slab * groups_per_bh, groups_per_bh) * kTileWaves + wave;
             if (c.tile >= a.num_tiles) continue;
-            if (a.seq_len && c.tile * 16 >= seq_length(a.seq_len, c.bh / a.H, a.n)) {
+            if (a.seq_len && c.tile * 16 >= seq_length_u(a.seq_len, c.bh / a.H, a.n)) {
                 const int64_t base = (int64_t)(c.bh / a.H) * a.sb + (int64_t)(c.bh % a.H) * a.sh;
                 float* qrow = a.dQ + base + (int64_t)(c.tile * 16 + r8) * a.sn + piece * 8;
 #pragma unroll
@@ -437,8 +437,8 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_q_tile_kernel(const TileA
                 if (lane < 16) a.stat[(int64_t)c.bh * a.N + c.tile * 16 + lane] = make_float2(kLseGone, 0.f);
                 continue;
             }
-            c.cp0 = a.chunk_ptr[c.tile];
-            c.npairs = (a.chunk_ptr[c.tile + 1] - c.cp0) >> 1;
+            c.cp0 = uniform_i32(a.chunk_ptr, c.tile);
+            c.npairs = (uniform_i32(a.chunk_ptr, c.tile + 1) - c.cp0) >> 1;
             c.valid = true;
             return;
         }
@@ -530,7 +530,7 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_q_tile_kernel(const TileA
             }
             if (a.seq_len) {   // uniform
                 wave_lds_sync();
-                mask_bias(a, bias_s, cc.tile * 16, seq_length(a.seq_len, cc.bh / a.H, a.n), g, j);
+                mask_bias(a, bias_s, cc.tile * 16, seq_length_u(a.seq_len, cc.bh / a.H, a.n), g, j);
             }
         }
         wave_lds_sync();  // the previous pair's reads of k_s, v_s (and the previous tile's of bias_s) are done
@@ -623,7 +623,7 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_q_tile_kernel(const TileA
             const int t0 = cc.tile * 16;
             float delta = dl_part + __shfl_xor(dl_part, 16);
             delta += __shfl_xor(delta, 32);
-            const int len = seq_length(a.seq_len, cc.bh / a.H, a.n);
+            const int len = seq_length_u(a.seq_len, cc.bh / a.H, a.n);
             if (g == 0) a.stat[(int64_t)cc.bh * a.N + t0 + j] = make_float2(t0 + j < len ? lse2 : kLseGone, delta);
             float* qrow_out = a.dQ + base + (int64_t)t0 * a.sn + j;
 #pragma unroll
@@ -725,10 +725,10 @@ __global__ void __launch_bounds__(kThreads, CPW == 2 ? 4 : 2) rel_grad_tile_kern
         const int bh = blk / blocks_per_bh, b2 = 2 * walk_pos(a.seq_len, bh, blk - bh * blocks_per_bh, blocks_per_bh), row0 = 16 * b2;
         const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
         // token tiles past the end of a shorter sequence were not computed: their slots do not count
-        const int len = seq_length(a.seq_len, bh / a.H, a.n);
-        s_begin = a.chunk_ptr[b2] * 256;
-        s_mid = a.chunk_ptr[min(b2 + 1, a.num_tiles)] * 256;
-        s_end = row0 + 16 < len ? a.chunk_ptr[min(b2 + 2, a.num_tiles)] * 256 : s_mid;
+        const int len = seq_length_u(a.seq_len, bh / a.H, a.n);
+        s_begin = uniform_i32(a.chunk_ptr, b2) * 256;
+        s_mid = uniform_i32(a.chunk_ptr, min(b2 + 1, a.num_tiles)) * 256;
+        s_end = row0 + 16 < len ? uniform_i32(a.chunk_ptr, min(b2 + 2, a.num_tiles)) * 256 : s_mid;
         qpiece = make_uint4(0u, 0u, 0u, 0u);
         if (threadIdx.x < kRgRows * 8) {
             const int r = threadIdx.x >> 3, c = (threadIdx.x & 7) * 8;
@@ -752,7 +752,7 @@ __global__ void __launch_bounds__(kThreads, CPW == 2 ? 4 : 2) rel_grad_tile_kern
         if (a.seq_len)
             for (; blk < total; blk += gridDim.x) {
                 const int bh = blk / blocks_per_bh;
-                if (walk_pos(a.seq_len, bh, blk - bh * blocks_per_bh, blocks_per_bh) * kRgRows < seq_length(a.seq_len, bh / a.H, a.n)) break;
+                if (walk_pos(a.seq_len, bh, blk - bh * blocks_per_bh, blocks_per_bh) * kRgRows < seq_length_u(a.seq_len, bh / a.H, a.n)) break;
             }
         return blk;
     };
