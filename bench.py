@@ -46,10 +46,61 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="lm")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layer", action="store_true",
+                    help="time the forward of one whole graph layer (projections, attention, FFN, normalisations; "
+                         "d_ff = 4 d) of the workload's shape instead of the attention path")
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="only run a plain device-to-device copy of this many MiB (10 times) and exit: the known "
                          "traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
     return ap.parse_args()
+
+
+def bench_layer(args, w, bpt, torch, np):
+    """Forward of one graph layer (Sec. 3.3) on the workload's shape: d = heads * 64, d_ff = 4 d, random bf16 weights."""
+    from paper_1911_04070_amd.workloads import make_lengths
+    d, d_ff = w.H * w.D, 4 * w.H * w.D
+    g = bpt.bpt_build_graph(w.n, w.k, w.causal)
+    gen = torch.Generator(device="cuda").manual_seed(1911 + w.index)
+    rnd = lambda *shape, s=1.0: (s * torch.randn(*shape, device="cuda", generator=gen))
+    X = rnd(w.B, g.num_nodes, d).to(torch.bfloat16)
+    X[:, w.n:] = 0                                            # span nodes start from zero
+    R = rnd(g.num_levels, g.rel_width, w.D, s=0.02).to(torch.bfloat16)
+    p = {k_: rnd(d, d, s=d ** -0.5).to(torch.bfloat16) for k_ in ("Wq", "Wk", "Wv", "Wo")}
+    p["W1"] = rnd(d, d_ff, s=d ** -0.5).to(torch.bfloat16)
+    p["W2"] = rnd(d_ff, d, s=d_ff ** -0.5).to(torch.bfloat16)
+    p.update(b1=rnd(d_ff, s=0.1), b2=rnd(d, s=0.1), g1=1 + rnd(d, s=0.1), beta1=rnd(d, s=0.1), g2=1 + rnd(d, s=0.1),
+             beta2=rnd(d, s=0.1))
+    lens_d = torch.from_numpy(make_lengths(w)).cuda() if w.length_mix else None
+    Y = torch.empty_like(X)
+    ws = torch.empty(int(bpt.load_library().bpt_layer_fwd_workspace(g.handle, w.B, w.H, d_ff)) + 256, dtype=torch.uint8,
+                     device="cuda")
+    step = lambda: bpt.bpt_layer_fwd(g, X, R, p, w.H, scale=w.scale, seq_len=lens_d, out=Y, workspace=ws)
+    for _ in range(args.warmup + 2):                         # the first GEMM calls load the library's kernels
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    bpt.bpt_profile_enable(True)
+    for _ in range(5):
+        step()
+    torch.cuda.synchronize()
+    own = {name: total / calls for name, (calls, total) in bpt.bpt_profile_report().items()}
+    bpt.bpt_profile_enable(False)
+    rows = w.B * g.num_nodes
+    flops = 2.0 * rows * (4 * d * d + 2 * d * d_ff)
+    print(json.dumps({
+        "metric": "BPT graph layer forward node rows/sec", "value": round(rows / (ms * 1e-3), 1), "unit": "rows/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
+        "dtype": "bf16", "data": "synthetic", "vs_baseline": None,
+        "config": {"workload": w.name + "+layer", "n": w.n, "k": w.k, "causal": w.causal, "batch": w.B, "heads": w.H,
+                   "d_model": d, "d_ff": d_ff, "node_rows": rows},
+        "dense_TFLOPs": round(flops / (ms * 1e-3) / 1e12, 1),
+        "own_kernel_ms": {k_: round(v, 4) for k_, v in sorted(own.items(), key=lambda kv: -kv[1])},
+        "gemm_and_gaps_ms": round(ms - sum(own.values()), 4),
+    }), flush=True)
 
 
 def main():
@@ -80,6 +131,8 @@ def main():
         build_library()
     w = WORKLOADS[args.workload]
     torch.cuda.set_device(0)
+    if args.layer:
+        return bench_layer(args, w, bpt, torch, np)
     tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
     bytes_scale = 1.0 if w.dtype == "bf16" else 2.0
 

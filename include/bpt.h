@@ -167,6 +167,37 @@ int bpt_attn_bwd_key_side(const bpt_graph_t* g, const bpt_shape_t* s, const void
 int bpt_profile_enable(int on);
 int64_t bpt_profile_report(char* buf, size_t capacity);
 
+/* Parameters of one graph layer (Sec. 3.1, Sec. 3.3): all device pointers, owned by the caller.
+ * d = H * 64.  A map is stored row-major as [inputs][outputs] and applied as y = x W; head i of
+ * Q, K, V is columns [64 i, 64 i + 64) of the projected features.  The paper writes the
+ * projections without a bias; the position-wise FFN and the layer normalisation carry theirs. */
+typedef struct {
+    const void *Wq, *Wk, *Wv, *Wo; /* [d][d] bf16 */
+    const void* W1;                /* [d][d_ff] bf16 */
+    const void* W2;                /* [d_ff][d] bf16 */
+    const float *b1, *b2;          /* [d_ff], [d] */
+    const float *g1, *beta1;       /* [d] gain and bias of the normalisation after attention */
+    const float *g2, *beta2;       /* [d] the same after the FFN */
+    int32_t d_ff;                  /* a multiple of 8 */
+    float eps;                     /* <= 0 selects 1e-5 */
+} bpt_layer_params_t;
+
+/* Sec. 3.1 (Transformer layer) and Sec. 3.3 (the update of the graph, one iteration of its
+ * loop), forward only, bf16:  Z = norm(X + GSA(G, X)),  Y = norm(Z + FFN(Z)),  with
+ * GSA(G, X) = [head_1 .. head_H] Wo, the heads being eq. (8) on Q = X Wq, K = X Wk, V = X Wv,
+ * FFN(z) = max(0, z W1 + b1) W2 + b2, norm = layer normalisation over the d features (biased
+ * variance).  X and Y are [B][N][d] bf16, contiguous, N = 2n-1 rows per batch entry in node-id
+ * order (span rows of the first layer are zero, Sec. 3.3); all nodes are updated from the same
+ * X.  rel, scale and seq_len as for bpt_attn_fwd (with seq_len, rows of nodes that are not
+ * kept hold unspecified values).  The dense maps run as rocBLAS GEMMs with fp32 accumulation;
+ * Q, K, V, the attention output, Z and the hidden FFN activations are stored in bf16.
+ * workspace: device memory of at least bpt_layer_fwd_workspace bytes; nothing is allocated
+ * except, once per device, the rocBLAS handle.  H * 64 <= 2048. */
+size_t bpt_layer_fwd_workspace(const bpt_graph_t* g, int32_t B, int32_t H, int32_t d_ff);
+int bpt_layer_fwd(const bpt_graph_t* g, int32_t B, int32_t H, float scale, const int32_t* seq_len, const void* rel,
+                  const void* X, const bpt_layer_params_t* p, void* Y, void* workspace, size_t workspace_bytes,
+                  void* stream);
+
 /* Sec. 3.2 with the rule for shorter sequences stated at the top of this header: the number
  * of edges of the graph over n tokens with density k that a sequence of len tokens keeps
  * (0 <= len <= n; len == n gives the graph's own edge count).  Host arithmetic only, no

@@ -23,7 +23,7 @@ EXPORTS = [
     "bpt_build_graph", "bpt_graph_info", "bpt_graph_csr", "bpt_graph_transposed", "bpt_graph_to_host",
     "bpt_graph_transposed_to_host", "bpt_graph_destroy", "bpt_attn_fwd_workspace", "bpt_attn_bwd_workspace",
     "bpt_attn_fwd", "bpt_attn_bwd", "bpt_attn_bwd_query_side", "bpt_attn_bwd_key_side", "bpt_profile_enable",
-    "bpt_profile_report", "bpt_count_edges", "bpt_strerror",
+    "bpt_profile_report", "bpt_layer_fwd_workspace", "bpt_layer_fwd", "bpt_count_edges", "bpt_strerror",
 ]
 
 
@@ -31,6 +31,11 @@ class BptShape(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("D", ctypes.c_int32), ("dtype", ctypes.c_int32),
                 ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64), ("stride_n", ctypes.c_int64),
                 ("scale", ctypes.c_float), ("seq_len", ctypes.c_void_p)]
+
+
+class BptLayerParams(ctypes.Structure):
+    _fields_ = [(name, ctypes.c_void_p) for name in ("Wq", "Wk", "Wv", "Wo", "W1", "W2", "b1", "b2", "g1", "beta1", "g2",
+                                                     "beta2")] + [("d_ff", ctypes.c_int32), ("eps", ctypes.c_float)]
 
 
 class BptError(RuntimeError):
@@ -84,6 +89,10 @@ def load_library() -> ctypes.CDLL:
     L.bpt_profile_enable.argtypes = [ctypes.c_int]
     L.bpt_profile_report.restype = ctypes.c_int64
     L.bpt_profile_report.argtypes = [ctypes.c_char_p, sz]
+    L.bpt_layer_fwd_workspace.restype = sz
+    L.bpt_layer_fwd_workspace.argtypes = [vp, i32, i32, i32]
+    L.bpt_layer_fwd.restype = ctypes.c_int
+    L.bpt_layer_fwd.argtypes = [vp, i32, i32, ctypes.c_float, vp, vp, vp, P(BptLayerParams), vp, vp, sz, vp]
     L.bpt_count_edges.restype = ctypes.c_int
     L.bpt_count_edges.argtypes = [i32, i32, i32, i32, P(i64)]
     L.bpt_strerror.restype = ctypes.c_char_p
@@ -294,6 +303,43 @@ def bpt_attn_bwd_key_side(g: Graph, Q, K, V, rel, lse, dout, dK, dV, workspace, 
                                    workspace.numel() * workspace.element_size(), _stream_ptr()),
            "bpt_attn_bwd_key_side")
     return dK, dV
+
+
+def bpt_layer_fwd(g: Graph, X: torch.Tensor, rel: torch.Tensor, params: dict, heads: int, scale: Optional[float] = None,
+                  eps: float = 1e-5, seq_len: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
+                  workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """One graph layer, forward (Sec. 3.3): X [B, N, heads*64] bf16 -> Y of the same shape.  params: Wq, Wk, Wv,
+    Wo [d, d], W1 [d, d_ff], W2 [d_ff, d] in bf16 and b1, b2, g1, beta1, g2, beta2 in fp32, all contiguous cuda tensors."""
+    L = load_library()
+    d = heads * 64
+    if X.dtype != torch.bfloat16 or X.dim() != 3 or X.shape[1] != g.num_nodes or X.shape[2] != d or not X.is_contiguous():
+        raise ValueError("X must be a contiguous bf16 [B, %d, %d] tensor" % (g.num_nodes, d))
+    if rel.dtype != torch.bfloat16 or tuple(rel.shape) != (g.num_levels, g.rel_width, 64) or not rel.is_contiguous():
+        raise ValueError("rel must be contiguous bf16 [%d,%d,64]" % (g.num_levels, g.rel_width))
+    d_ff = params["W1"].shape[1]
+    want = {"Wq": (d, d), "Wk": (d, d), "Wv": (d, d), "Wo": (d, d), "W1": (d, d_ff), "W2": (d_ff, d), "b1": (d_ff,),
+            "b2": (d,), "g1": (d,), "beta1": (d,), "g2": (d,), "beta2": (d,)}
+    for name, shape in want.items():
+        t = params[name]
+        dt = torch.bfloat16 if name.startswith("W") else torch.float32
+        if t.dtype != dt or tuple(t.shape) != shape or not t.is_contiguous() or t.device != X.device:
+            raise ValueError("parameter %s must be a contiguous %s tensor of shape %s on the device of X" % (name, dt, shape))
+    lens = None
+    if seq_len is not None:
+        if seq_len.dtype != torch.int32 or tuple(seq_len.shape) != (X.shape[0],) or not seq_len.is_contiguous():
+            raise ValueError("seq_len must be a contiguous int32 tensor of B entries")
+        lens = seq_len.data_ptr()
+    lp = BptLayerParams(*[params[n].data_ptr() for n in ("Wq", "Wk", "Wv", "Wo", "W1", "W2", "b1", "b2", "g1", "beta1",
+                                                          "g2", "beta2")], d_ff, float(eps))
+    if out is None:
+        out = torch.empty_like(X)
+    need = int(L.bpt_layer_fwd_workspace(g.handle, X.shape[0], heads, d_ff))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=X.device)
+    _check(L.bpt_layer_fwd(g.handle, X.shape[0], heads, float(scale) if scale else 0.0, lens, rel.data_ptr(), X.data_ptr(),
+                           ctypes.byref(lp), out.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream_ptr()),
+           "bpt_layer_fwd")
+    return out
 
 
 def bpt_profile_enable(on: bool) -> None:

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libbpt.so")
-SOURCES = ["bpt_graph.hip", "bpt_tiles.hip", "bpt_attn.hip"]
+SOURCES = ["bpt_graph.hip", "bpt_tiles.hip", "bpt_attn.hip", "bpt_layer.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-munsafe-fp-atomics",
     # packed fp32 VALU forms are kept off on the test machines
@@ -22,6 +22,7 @@ def build_library(verbose: bool = False) -> str:
     tmp = LIB + ".tmp.%d" % os.getpid()
     cmd = [hipcc] + FLAGS + ["-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", tmp]
     cmd += [os.path.join(CSRC, s) for s in SOURCES]
+    cmd += ["-L/opt/rocm/lib", "-lrocblas", "-Wl,-rpath,/opt/rocm/lib"]   # plain library GEMMs of the graph layer
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
