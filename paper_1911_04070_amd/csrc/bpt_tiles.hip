@@ -15,6 +15,7 @@ constexpr int kTB = 256;
 constexpr int kScanItems = 16;
 constexpr int kScanBlock = kTB * kScanItems;   // elements per block of the scan
 constexpr int kMaxLevels = 24;                 // n <= 2^22
+constexpr int kMaxSortedTasks = 1 << 16;       // key-tile tasks are put in stretch order up to this many (the ordering is quadratic)
 constexpr int kMaxBuckets = 2 * kMaxLevels;
 
 __host__ __device__ inline int level_off(int n, int level) { return 2 * n - ((2 * n) >> level); }
@@ -362,6 +363,45 @@ __global__ void key_tile_tasks(int nkt, int task_chunks, int num_multi, int num_
     }
 }
 
+// Orders the tasks by the stretch of kSegTokens tokens in which their query lists begin, and inside
+// a stretch keeps the order of the tiles (level-major).  All levels of one stretch then run
+// together and read its Q and dO rows while they are in the L2 of the XCD, instead of every level
+// sweeping the whole sequence again (the rows of one (batch, head) are about as large as that
+// L2).  Keeping the tile order inside a stretch keeps the long tasks of the coarse levels next to
+// each other, so that they land on different wavefronts as before.  One thread per task counts
+// the tasks that come before it.  Which wavefront computes a task changes no result: partial sums
+// keep their slots.
+constexpr int kSegTokens = 2048;
+__global__ void key_tile_task_order(int num_tasks, int n, const int32_t* __restrict__ cols,
+                                    const int32_t* __restrict__ in_tile, const int32_t* __restrict__ in_c0,
+                                    const int32_t* __restrict__ in_nch, const int32_t* __restrict__ in_part,
+                                    int32_t* __restrict__ task_tile, int32_t* __restrict__ task_c0,
+                                    int32_t* __restrict__ task_nch, int32_t* __restrict__ task_part) {
+    __shared__ int32_t keys_s[kTB];
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    // a list that begins with a span node (only ancestors) belongs to the last stretch
+    auto key_of = [&](int task) { return min(cols[(int64_t)in_c0[task] * 16], n - 1) / kSegTokens; };
+    const int mine = t < num_tasks ? key_of(t) : 0;
+    int rank = 0;
+    for (int base = 0; base < num_tasks; base += kTB) {
+        const int o = base + (int)threadIdx.x;
+        keys_s[threadIdx.x] = o < num_tasks ? key_of(o) : 0x7FFFFFFF;
+        __syncthreads();
+        const int lim = min(kTB, num_tasks - base);
+        for (int i = 0; i < lim; ++i) {
+            const int other = keys_s[i];
+            rank += (other < mine || (other == mine && base + i < t)) ? 1 : 0;
+        }
+        __syncthreads();
+    }
+    if (t < num_tasks) {
+        task_tile[rank] = in_tile[t];
+        task_c0[rank] = in_c0[t];
+        task_nch[rank] = in_nch[t];
+        task_part[rank] = in_part[t];
+    }
+}
+
 template <typename T>
 int device_alloc(T** p, size_t count) {
     BPT_HIP(hipMalloc((void**)p, std::max<size_t>(count, 1) * sizeof(T)));
@@ -483,11 +523,26 @@ int build_tile_metadata(bpt_graph* g, const int32_t* cnt_l, const int32_t* min_l
         const int token_tiles = lb.tile_base[1];
         hipLaunchKernelGGL(key_tile_map_ancestors, dim3((token_tiles * 16 + kTB - 1) / kTB), dim3(kTB), 0, st, num_levels, W,
                            token_tiles, kt.chunk_ptr, kt.tile_node0, kt.tile_info, anc_first.as<int32_t>(), kt.map);
+        const bool reorder = n > kSegTokens && num_tasks <= kMaxSortedTasks;
+        DeviceBuf ut_tile, ut_c0, ut_nch, ut_part;   // the tasks in tile order, when they are put in another one
+        if (reorder) {
+            const size_t tbytes = sizeof(int32_t) * (size_t)std::max(num_tasks, 1);
+            BPT_HIP(ut_tile.alloc(tbytes));
+            BPT_HIP(ut_c0.alloc(tbytes));
+            BPT_HIP(ut_nch.alloc(tbytes));
+            BPT_HIP(ut_part.alloc(tbytes));
+        }
         hipLaunchKernelGGL(key_tile_tasks, dim3((nkt + kTB - 1) / kTB), dim3(kTB), 0, st, nkt, task_chunks, num_multi,
                            num_part, kt.chunk_ptr, ntask.as<int32_t>(), task_ptr.as<int32_t>(), part_base.as<int32_t>(),
-                           multi_idx.as<int32_t>(), kt.task_tile, kt.task_c0, kt.task_nch, kt.task_part, kt.multi_tile,
-                           kt.multi_ptr);
+                           multi_idx.as<int32_t>(), reorder ? ut_tile.as<int32_t>() : kt.task_tile,
+                           reorder ? ut_c0.as<int32_t>() : kt.task_c0, reorder ? ut_nch.as<int32_t>() : kt.task_nch,
+                           reorder ? ut_part.as<int32_t>() : kt.task_part, kt.multi_tile, kt.multi_ptr);
+        if (reorder && num_tasks > 0)
+            hipLaunchKernelGGL(key_tile_task_order, dim3((num_tasks + kTB - 1) / kTB), dim3(kTB), 0, st, num_tasks, n, kt.cols,
+                               ut_tile.as<int32_t>(), ut_c0.as<int32_t>(), ut_nch.as<int32_t>(), ut_part.as<int32_t>(),
+                               kt.task_tile, kt.task_c0, kt.task_nch, kt.task_part);
         BPT_HIP(hipGetLastError());
+        if (reorder) BPT_HIP(hipStreamSynchronize(st));   // the lists in tile order are freed at the end of this block
         kt.num_chunks = (int32_t)kchunks;
         kt.nb_pad = (W + num_levels - 1 + 15) & ~15;
         kt.first_uncovered = level_off(n, ctx_levels);
