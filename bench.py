@@ -27,16 +27,16 @@ HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
 # workload; the runs and their commands are in profiles/.  None where not measured.
 MEASURED_TRAFFIC = {
     "lm": {  # profiles/lm_n8192_k8_causal_bf16_kernels.md
-        "bwd_kv_tile_kernel": int((311688.7 * 2.0 + 278797.4) * 1024),
-        "bwd_q_tile_kernel": int((144535.4 * 2.0 + 309288.4) * 1024),
-        "rel_grad_tile_kernel": int((173310.2 * 2.0 + 90112.8) * 1024),
-        "fwd_tile_kernel": int((117098.8 * 2.0 + 33873.4) * 1024),
-        "bwd_q_span_tile_kernel": int((67584.0 * 2.0 + 99544.1) * 1024),
-        "fwd_span_tile_kernel": int((49585.8 * 2.0 + 49983.9) * 1024),
+        "bwd_kv_tile_kernel": int((322754.0 * 2.0 + 278784.0) * 1024),
+        "bwd_q_tile_kernel": int((144196.4 * 2.0 + 309269.9) * 1024),
+        "rel_grad_tile_kernel": int((173082.0 * 2.0 + 90112.3) * 1024),
+        "fwd_tile_kernel": int((117065.4 * 2.0 + 33873.9) * 1024),
+        "bwd_q_span_tile_kernel": int((67578.0 * 2.0 + 99726.8) * 1024),
+        "fwd_span_tile_kernel": int((49578.9 * 2.0 + 49978.8) * 1024),
     },
 }
 # HBM bytes of one whole step (all kernels, same counters and scaling)
-MEASURED_STEP_TRAFFIC = {"lm": 2763413708}
+MEASURED_STEP_TRAFFIC = {"lm": 2784974950}
 
 
 def parse():
