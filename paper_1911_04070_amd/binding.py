@@ -342,6 +342,32 @@ def bpt_layer_fwd(g: Graph, X: torch.Tensor, rel: torch.Tensor, params: dict, he
     return out
 
 
+class GraphAttentionFunction(torch.autograd.Function):
+    """Graph self-attention (eq. (8)) as a torch.autograd.Function: the forward and the backward are
+    the library's bpt_attn_fwd / bpt_attn_bwd, nothing is computed in Python.  Gradients come back
+    in fp32 and are cast to the dtype of their inputs."""
+
+    @staticmethod
+    def forward(ctx, g, Q, K, V, rel, scale, seq_len):
+        out, lse = bpt_attn_fwd(g, Q, K, V, rel, scale=scale, seq_len=seq_len)
+        ctx.save_for_backward(Q, K, V, rel, lse)
+        ctx.g, ctx.scale, ctx.seq_len = g, scale, seq_len
+        return out
+
+    @staticmethod
+    def backward(ctx, dout):
+        Q, K, V, rel, lse = ctx.saved_tensors
+        if dout.stride() != Q.stride():
+            dout = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device).copy_(dout)
+        dQ, dK, dV, d_rel = bpt_attn_bwd(ctx.g, Q, K, V, rel, lse, dout.to(Q.dtype), scale=ctx.scale, seq_len=ctx.seq_len)
+        return None, dQ.to(Q.dtype), dK.to(K.dtype), dV.to(V.dtype), d_rel.to(rel.dtype), None, None
+
+
+def graph_attention(g: Graph, Q, K, V, rel, scale: Optional[float] = None, seq_len: Optional[torch.Tensor] = None):
+    """out = graph self-attention of eq. (8), differentiable with respect to Q, K, V and rel."""
+    return GraphAttentionFunction.apply(g, Q, K, V, rel, scale, seq_len)
+
+
 def bpt_profile_enable(on: bool) -> None:
     _check(load_library().bpt_profile_enable(int(bool(on))), "bpt_profile_enable")
 

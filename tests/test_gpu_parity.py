@@ -287,6 +287,22 @@ def test_lengths_equal_to_n_change_nothing():
     g.destroy()
 
 
+def test_autograd_function_returns_the_library_gradients():
+    w = Workload("autograd", 24, 256, 3, False, 2, 2, 64, "f32", True)
+    x = make_inputs(w)
+    g = bpt.bpt_build_graph(w.n, w.k, w.causal)
+    Q, K, V, R, dO = (to_dev(x[k], "f32") for k in ("Q", "K", "V", "Rel", "dO"))
+    leaves = [t.clone().requires_grad_(True) for t in (Q, K, V, R)]
+    out = bpt.graph_attention(g, *leaves, scale=w.scale)
+    out.backward(dO)
+    ref_out, lse = bpt.bpt_attn_fwd(g, Q, K, V, R, scale=w.scale)
+    ref = bpt.bpt_attn_bwd(g, Q, K, V, R, lse, dO, scale=w.scale)
+    assert torch.equal(out.detach(), ref_out)
+    for leaf, r in zip(leaves, ref):
+        assert torch.equal(leaf.grad, r)
+    g.destroy()
+
+
 def test_scale_argument_and_default():
     w = Workload("scale", 10, 256, 2, False, 1, 2, 64, "f32", True)
     x = make_inputs(w)
