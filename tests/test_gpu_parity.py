@@ -287,6 +287,24 @@ def test_lengths_equal_to_n_change_nothing():
     g.destroy()
 
 
+def test_random_small_configurations():
+    # seeded draws over sizes, densities, direction, batch shape, dtype and lengths: every kernel family
+    # and every switch between them gets hit with shapes nobody picked by hand
+    rng = np.random.default_rng(20191111)
+    for case in range(24):
+        n = int(2 ** rng.integers(1, 11))
+        k = int(rng.integers(1, 2 * n + 2)) if rng.random() < 0.3 else int(rng.integers(1, 12))
+        causal = bool(rng.integers(0, 2))
+        B, H = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        dtype = "bf16" if rng.random() < 0.7 else "f32"
+        w = Workload("random%d" % case, 30 + case, n, k, causal, B, H, 64, dtype, True)
+        if rng.random() < 0.5:
+            lengths = [int(rng.integers(0 if rng.random() < 0.1 else 1, n + 1)) for _ in range(B)]
+            run_lengths_case(w, lengths)
+        else:
+            run_case(w)
+
+
 def test_autograd_function_returns_the_library_gradients():
     w = Workload("autograd", 24, 256, 3, False, 2, 2, 64, "f32", True)
     x = make_inputs(w)
