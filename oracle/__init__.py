@@ -57,9 +57,9 @@ def _load():
         L.bpto_transpose.restype = None
         L.bpto_transpose.argtypes = [i32, p, p, p, p, p]
         L.bpto_attn_fwd.restype = i32
-        L.bpto_attn_fwd.argtypes = [i32, p, p, p, i32, i32, p, p, p, p, f64, p, p, i32]
+        L.bpto_attn_fwd.argtypes = [i32, p, p, p, i32, i32, p, p, p, p, f64, p, p, i32, f64, ctypes.c_uint32, i32]
         L.bpto_attn_bwd.restype = i32
-        L.bpto_attn_bwd.argtypes = [i32, p, p, p, i32, i32, i32, p, p, p, p, p, f64, p, p, p, p, i32]
+        L.bpto_attn_bwd.argtypes = [i32, p, p, p, i32, i32, i32, p, p, p, p, p, f64, p, p, p, p, i32, f64, ctypes.c_uint32, i32]
         _lib = L
     return _lib
 
@@ -155,8 +155,9 @@ def _as_bhnd(x: np.ndarray, N: int):
     return x
 
 
-def attn_fwd(g: Graph, Q, K, V, Rel, scale: float, threads: int = 0):
-    """Eq. (8) per node in float64.  Q,K,V: [B,H,N,D]; Rel: [levels,W,D].
+def attn_fwd(g: Graph, Q, K, V, Rel, scale: float, threads: int = 0, dropout=0.0, seed=0, bh0=0):
+    """Eq. (8) per node in float64.  Q,K,V: [B,H,N,D]; Rel: [levels,W,D].  dropout, seed: inverted dropout on the
+    attention weights with the counter-based mask of the C source; bh0: index of this call's first (batch, head).
 
     Returns (out [B,H,N,D] f64, lse [B,H,N] f64, threads_used)."""
     L = _load()
@@ -169,11 +170,12 @@ def attn_fwd(g: Graph, Q, K, V, Rel, scale: float, threads: int = 0):
     out = np.zeros((B, H, N, D), dtype=np.float64)
     lse = np.zeros((B, H, N), dtype=np.float64)
     used = L.bpto_attn_fwd(N, _ptr(g.row_ptr), _ptr(g.col), _ptr(g.rel), B * H, D, _ptr(Q), _ptr(K),
-                           _ptr(V), _ptr(Rel), float(scale), _ptr(out), _ptr(lse), int(threads))
+                           _ptr(V), _ptr(Rel), float(scale), _ptr(out), _ptr(lse), int(threads), float(dropout),
+                           int(seed) & 0xFFFFFFFF, int(bh0))
     return out, lse, int(used)
 
 
-def attn_bwd(g: Graph, Q, K, V, Rel, dO, scale: float, threads: int = 0):
+def attn_bwd(g: Graph, Q, K, V, Rel, dO, scale: float, threads: int = 0, dropout=0.0, seed=0, bh0=0):
     """Gradient of eq. (8) in float64.  Returns (dQ, dK, dV, dRel, threads_used)."""
     L = _load()
     Q = _as_bhnd(Q, g.num_nodes)
@@ -189,11 +191,12 @@ def attn_bwd(g: Graph, Q, K, V, Rel, dO, scale: float, threads: int = 0):
     dRel = np.zeros((g.num_levels, g.rel_width, D), dtype=np.float64)
     used = L.bpto_attn_bwd(N, _ptr(g.row_ptr), _ptr(g.col), _ptr(g.rel), B * H, D,
                            g.num_levels * g.rel_width, _ptr(Q), _ptr(K), _ptr(V), _ptr(Rel), _ptr(dO),
-                           float(scale), _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(dRel), int(threads))
+                           float(scale), _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(dRel), int(threads), float(dropout),
+                           int(seed) & 0xFFFFFFFF, int(bh0))
     return dQ, dK, dV, dRel, int(used)
 
 
-def attn_fwd_lengths(n, k, causal, lengths, Q, K, V, Rel, scale: float, threads: int = 0):
+def attn_fwd_lengths(n, k, causal, lengths, Q, K, V, Rel, scale: float, threads: int = 0, dropout=0.0, seed=0):
     """Forward of a batch whose b-th sequence has lengths[b] tokens: every batch entry runs
     on the graph of its own length.  Returns (out, lse, edges) with edges = edge count of
     the whole batch per head."""
@@ -203,11 +206,12 @@ def attn_fwd_lengths(n, k, causal, lengths, Q, K, V, Rel, scale: float, threads:
     for b, length in enumerate(lengths):
         g = build_graph_len(n, int(length), k, causal)
         edges += g.num_edges
-        out[b:b + 1], lse[b:b + 1], _ = attn_fwd(g, Q[b:b + 1], K[b:b + 1], V[b:b + 1], Rel, scale, threads)
+        out[b:b + 1], lse[b:b + 1], _ = attn_fwd(g, Q[b:b + 1], K[b:b + 1], V[b:b + 1], Rel, scale, threads, dropout, seed,
+                                                 b * np.shape(Q)[1])
     return out, lse, edges
 
 
-def attn_bwd_lengths(n, k, causal, lengths, Q, K, V, Rel, dO, scale: float, threads: int = 0):
+def attn_bwd_lengths(n, k, causal, lengths, Q, K, V, Rel, dO, scale: float, threads: int = 0, dropout=0.0, seed=0):
     """Gradient of a batch of sequences of different lengths; dRel is summed over the batch."""
     dQ = np.zeros(np.shape(Q), dtype=np.float64)
     dK = np.zeros_like(dQ)
@@ -215,7 +219,8 @@ def attn_bwd_lengths(n, k, causal, lengths, Q, K, V, Rel, dO, scale: float, thre
     dRel = None
     for b, length in enumerate(lengths):
         g = build_graph_len(n, int(length), k, causal)
-        q, kk, v, r, _ = attn_bwd(g, Q[b:b + 1], K[b:b + 1], V[b:b + 1], Rel, dO[b:b + 1], scale, threads)
+        q, kk, v, r, _ = attn_bwd(g, Q[b:b + 1], K[b:b + 1], V[b:b + 1], Rel, dO[b:b + 1], scale, threads, dropout, seed,
+                                  b * np.shape(Q)[1])
         dQ[b:b + 1], dK[b:b + 1], dV[b:b + 1] = q, kk, v
         dRel = r if dRel is None else dRel + r
     return dQ, dK, dV, dRel

@@ -46,6 +46,14 @@
  * last kept node and the side stops there.  Ids stay those of the tree over n, so
  * rows of nodes that are not kept are empty; their output is defined as zero.
  *
+ * Dropout on the attention weights (p_a of the hyper-parameter tables; the paper gives no formula):
+ * the usual inverted dropout after the softmax -- weight p_e becomes keep_e p_e / (1 - p_a) in the
+ * weighted sum of values, lse is that of the full softmax -- with keep_e drawn from a counter-based
+ * hash of (seed, batch*heads index, query node, x_e), x_e = relative-position id of the edge for a
+ * token row and 2^31 + key node for a span row (both identify the edge within its row):
+ *   mix(z): z ^= z>>16; z *= 0x7FEB352D; z ^= z>>15; z *= 0x846CA68B; z ^= z>>16   (32-bit)
+ *   keep = mix(mix(mix(seed ^ (0x9E3779B9 * bh)) + u) + x) >= floor(p_a * 2^32).
+ *
  * Node ids: level-major, id(l,m) = off(l) + m with off(l) = 2n - (2n >> l);
  * tokens are 0..n-1 and the root is 2n-2.
  *
@@ -336,6 +344,26 @@ int32_t bpto_build_graph_len(int32_t n, int32_t len, int32_t k, int32_t causal,
     return e == E ? 0 : -1;
 }
 
+/* ---- dropout mask ------------------------------------------------------------- */
+static uint32_t mix32(uint32_t z)
+{
+    z ^= z >> 16; z *= 0x7FEB352Du; z ^= z >> 15; z *= 0x846CA68Bu; z ^= z >> 16;
+    return z;
+}
+static uint32_t drop_threshold(double p)
+{
+    double t = floor(p * 4294967296.0);
+    return t <= 0.0 ? 0u : (t >= 4294967295.0 ? 4294967295u : (uint32_t)t);
+}
+/* 1/(1-p) if the edge is kept, else 0; p <= 0 keeps everything */
+static double keep_scale(double p, uint32_t thr, uint32_t seed, int64_t bh, int32_t n_tokens, int32_t u, int32_t v, int32_t rel)
+{
+    if (p <= 0.0) return 1.0;
+    uint32_t x = u < n_tokens ? (uint32_t)rel : (0x80000000u + (uint32_t)v);
+    uint32_t r = mix32(mix32(mix32(seed ^ (0x9E3779B9u * (uint32_t)bh)) + (uint32_t)u) + x);
+    return r >= thr ? 1.0 / (1.0 - p) : 0.0;
+}
+
 /* ---- attention, eq. (6)/(8) -------------------------------------------- */
 
 /* scores of one row into s[], returns lse */
@@ -369,8 +397,11 @@ static int32_t max_degree(int32_t N, const int32_t *row_ptr)
  * lse: [BH][N] double.  threads <= 0 means all cores. Returns threads used. */
 int32_t bpto_attn_fwd(int32_t N, const int32_t *row_ptr, const int32_t *col, const int32_t *rel,
                       int32_t BH, int32_t D, const float *Q, const float *K, const float *V,
-                      const float *Rel, double scale, double *out, double *lse, int32_t threads)
+                      const float *Rel, double scale, double *out, double *lse, int32_t threads,
+                      double p_drop, uint32_t seed, int32_t bh0)
 {
+    const uint32_t thr = drop_threshold(p_drop);
+    const int32_t n_tokens = (N + 1) / 2;
     int32_t used = 1;
     int32_t md = max_degree(N, row_ptr);
 #ifdef _OPENMP
@@ -393,7 +424,7 @@ int32_t bpto_attn_fwd(int32_t N, const int32_t *row_ptr, const int32_t *col, con
                 double *o = out + ((int64_t)bh * N + u) * D;
                 for (int32_t d = 0; d < D; ++d) o[d] = 0.0;
                 for (int32_t e = 0; e < deg; ++e) {
-                    double p = exp(s[e] - l);
+                    double p = exp(s[e] - l) * keep_scale(p_drop, thr, seed, (int64_t)bh0 + bh, n_tokens, u, col[b + e], rel[b + e]);
                     const float *vv = Vbh + (int64_t)col[b + e] * D;
                     for (int32_t d = 0; d < D; ++d) o[d] += p * (double)vv[d];
                 }
@@ -415,8 +446,13 @@ int32_t bpto_attn_fwd(int32_t N, const int32_t *row_ptr, const int32_t *col, con
 int32_t bpto_attn_bwd(int32_t N, const int32_t *row_ptr, const int32_t *col, const int32_t *rel,
                       int32_t BH, int32_t D, int32_t num_ids, const float *Q, const float *K,
                       const float *V, const float *Rel, const float *dO, double scale, double *dQ,
-                      double *dK, double *dV, double *dRel, int32_t threads)
+                      double *dK, double *dV, double *dRel, int32_t threads,
+                      double p_drop, uint32_t seed, int32_t bh0)
 {
+    /* with dropout, out_u = sum_e m_e p_e v_v (m_e = keep/(1-p_a)): dP_e = m_e dO_u . v_v,
+     * delta_u = sum_e p_e dP_e = dO_u . out_u, dV_v += m_e p_e dO_u; the rest is unchanged */
+    const uint32_t thr = drop_threshold(p_drop);
+    const int32_t n_tokens = (N + 1) / 2;
     int32_t used = 1;
     int32_t md = max_degree(N, row_ptr);
 #ifdef _OPENMP
@@ -445,7 +481,7 @@ int32_t bpto_attn_bwd(int32_t N, const int32_t *row_ptr, const int32_t *col, con
                 double l = row_scores(q, K + base, Rel, D, col + b, rel + b, deg, scale, s);
                 for (int32_t d = 0; d < D; ++d) o[d] = 0.0;
                 for (int32_t e = 0; e < deg; ++e) {
-                    double p = exp(s[e] - l);
+                    double p = exp(s[e] - l) * keep_scale(p_drop, thr, seed, (int64_t)bh0 + bh, n_tokens, u, col[b + e], rel[b + e]);
                     const float *vv = V + base + (int64_t)col[b + e] * D;
                     for (int32_t d = 0; d < D; ++d) o[d] += p * (double)vv[d];
                 }
@@ -457,14 +493,16 @@ int32_t bpto_attn_bwd(int32_t N, const int32_t *row_ptr, const int32_t *col, con
                     const float *kv = K + base + v * D, *vv = V + base + v * D;
                     const float *r = Rel + (int64_t)rel[b + e] * D;
                     double p = exp(s[e] - l), dP = 0.0;
+                    const double m = keep_scale(p_drop, thr, seed, (int64_t)bh0 + bh, n_tokens, u, (int32_t)v, rel[b + e]);
                     for (int32_t d = 0; d < D; ++d) dP += (double)g[d] * (double)vv[d];
+                    dP *= m;
                     double dS = p * (dP - delta);
                     double *dk = dK + base + v * D, *dv = dV + base + v * D;
                     double *dr = dR + (int64_t)rel[b + e] * D;
                     for (int32_t d = 0; d < D; ++d) {
                         dq[d] += scale * dS * ((double)kv[d] + (double)r[d]);
                         dk[d] += scale * dS * (double)q[d];
-                        dv[d] += p * (double)g[d];
+                        dv[d] += m * p * (double)g[d];
                         dr[d] += scale * dS * (double)q[d];
                     }
                 }

@@ -282,3 +282,74 @@ def test_rows_that_are_not_kept_have_no_influence():
         oracle.attn_bwd_lengths(n, k, False, lengths, Q2, K2, V2, Rel, dO2, scale)
     for x, y in zip(a, b2):
         assert np.array_equal(x, y)
+
+
+# ------------------------------------------------ dropout on the attention weights
+def keep_mask(g, B, H, p, seed):
+    """The documented mask, restated with numpy uint32 arithmetic: [B*H, N, N] of 0 / 1/(1-p)."""
+    def mix(z):
+        z = z ^ (z >> np.uint32(16))
+        z = z * np.uint32(0x7FEB352D)
+        z = z ^ (z >> np.uint32(15))
+        z = z * np.uint32(0x846CA68B)
+        return z ^ (z >> np.uint32(16))
+    N = g.num_nodes
+    thr = np.uint32(min(int(np.floor(p * 2.0 ** 32)), 2 ** 32 - 1))
+    M = np.zeros((B * H, N, N))
+    with np.errstate(over="ignore"):
+        for bh in range(B * H):
+            h0 = mix(np.uint32(seed) ^ (np.uint32(0x9E3779B9) * np.uint32(bh)))
+            for u in range(N):
+                b, e = g.row_ptr[u], g.row_ptr[u + 1]
+                cols, rels = g.col[b:e].astype(np.uint32), g.rel[b:e].astype(np.uint32)
+                x = rels if u < g.n else np.uint32(0x80000000) + cols
+                r = mix(mix(h0 + np.uint32(u)) + x)
+                M[bh, u, g.col[b:e]] = np.where(r >= thr, 1.0 / (1.0 - p), 0.0)
+    return M.reshape(B, H, N, N)
+
+
+@pytest.mark.parametrize("n,k,causal,p", [(16, 2, False, 0.1), (32, 3, True, 0.5), (8, 1, False, 0.9)])
+def test_dropout_equals_dense_attention_with_the_documented_mask(n, k, causal, p):
+    g = oracle.build_graph(n, k, causal)
+    B, H, D = 2, 2, 8
+    Q, K, V, Rel, dO = rand_inputs(g, B, H, D, seed=n + 3)
+    scale, seed = 0.3, 123456789
+    M = keep_mask(g, B, H, p, seed)
+    mask, ids = dense_mask_and_ids(g)
+    Qt, Kt, Vt = (torch.tensor(x, dtype=torch.float64, requires_grad=True) for x in (Q, K, V))
+    Rt = torch.tensor(Rel, dtype=torch.float64, requires_grad=True)
+    R = Rt.reshape(-1, D)[torch.tensor(ids)]
+    S = scale * (torch.einsum("bhud,bhvd->bhuv", Qt, Kt) + torch.einsum("bhud,uvd->bhuv", Qt, R))
+    S = S.masked_fill(~torch.tensor(mask), float("-inf"))
+    P = torch.softmax(S, -1)
+    out_t = (P * torch.tensor(M)) @ Vt
+    out_t.backward(torch.tensor(dO, dtype=torch.float64))
+    out, lse, _ = oracle.attn_fwd(g, Q, K, V, Rel, scale, dropout=p, seed=seed)
+    grads = oracle.attn_bwd(g, Q, K, V, Rel, dO, scale, dropout=p, seed=seed)
+    assert np.abs(out - out_t.detach().numpy()).max() < 1e-12
+    assert np.abs(lse - torch.logsumexp(S, -1).detach().numpy()).max() < 1e-12      # lse is that of the full softmax
+    for got, leaf in zip(grads[:4], (Qt, Kt, Vt, Rt)):
+        assert np.abs(got - leaf.grad.numpy()).max() < 1e-11
+    # the kept fraction is about 1 - p, and the mask differs between heads and between seeds
+    edges = mask.sum() * B * H
+    kept = (M > 0).sum() / edges
+    assert abs(kept - (1 - p)) < 4 * np.sqrt(p * (1 - p) / edges) + 0.01
+    assert not np.array_equal(M[0, 0], M[0, 1])
+    assert not np.array_equal(M, keep_mask(g, B, H, p, seed + 1))
+
+
+def test_dropout_zero_is_no_dropout_and_lengths_use_global_head_indices():
+    g = oracle.build_graph(32, 2, False)
+    Q, K, V, Rel, dO = rand_inputs(g, 3, 2, 8, seed=8)
+    a = oracle.attn_fwd(g, Q, K, V, Rel, 0.2)[0]
+    b = oracle.attn_fwd(g, Q, K, V, Rel, 0.2, dropout=0.0, seed=99)[0]
+    assert np.array_equal(a, b)
+    # a batch of full lengths through the per-entry path draws the same masks as one call
+    c = oracle.attn_fwd(g, Q, K, V, Rel, 0.2, dropout=0.3, seed=5)[0]
+    d = oracle.attn_fwd_lengths(32, 2, False, [32, 32, 32], Q, K, V, Rel, 0.2, dropout=0.3, seed=5)[0]
+    assert np.array_equal(c, d)
+    ga = oracle.attn_bwd(g, Q, K, V, Rel, dO, 0.2, dropout=0.3, seed=5)
+    gb = oracle.attn_bwd_lengths(32, 2, False, [32, 32, 32], Q, K, V, Rel, dO, 0.2, dropout=0.3, seed=5)
+    for x, y in zip(ga[:3], gb[:3]):
+        assert np.array_equal(x, y)
+    assert np.abs(ga[3] - gb[3]).max() < 1e-12
