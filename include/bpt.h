@@ -33,6 +33,16 @@
  *     (the same for all of them); lse is contiguous [B][H][N] fp32.
  *   - Outputs are fully overwritten, never accumulated into.
  *
+ * Dropout on the attention weights (p_a in the paper's hyper-parameter tables, which give the
+ * rate and no formula): inverted dropout after the softmax.  With rate p the output is
+ * out_u = sum_e keep_e p_e v_v / (1 - p); lse is that of the full softmax; the backward uses the
+ * same mask (pass the same dropout_p and dropout_seed to forward and backward).  keep_e is a
+ * counter-based hash, so that no mask is stored and every kernel that meets an edge can form it:
+ *   mix(z): z ^= z >> 16; z *= 0x7FEB352D; z ^= z >> 15; z *= 0x846CA68B; z ^= z >> 16  (32 bit)
+ *   keep_e = mix(mix(mix(seed ^ 0x9E3779B9 * bh) + u) + x_e) >= floor(p * 2^32),
+ * bh = b * H + h, u = query node, x_e = relative-position id of the edge for a token row and
+ * 2^31 + key node for a span row.  Use a fresh seed per layer and step.
+ *
  * Sequences shorter than n (batches of sequences of different lengths).  The paper
  * states the tree for n a power of two (Sec. 3.2.1).  A batch entry b with
  * len = seq_len[b] < n tokens lives on the same node ids and keeps the nodes that hold
@@ -74,6 +84,8 @@ typedef struct {
     float scale;         /* softmax scale; <= 0 selects 1/sqrt(D) (Sec. 3.1 eq. (6)) */
     const int32_t* seq_len; /* device pointer to B token counts, or NULL: every sequence has n
                               tokens.  See "Sequences shorter than n" above. */
+    float dropout_p;     /* dropout rate on the attention weights, 0 <= p < 1; 0: none.  See below. */
+    uint32_t dropout_seed;
 } bpt_shape_t;
 
 /* Sec. 3.2 + Algorithm 1.  Builds, on the current device, the graph of a

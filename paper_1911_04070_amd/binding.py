@@ -30,7 +30,8 @@ EXPORTS = [
 class BptShape(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("D", ctypes.c_int32), ("dtype", ctypes.c_int32),
                 ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64), ("stride_n", ctypes.c_int64),
-                ("scale", ctypes.c_float), ("seq_len", ctypes.c_void_p)]
+                ("scale", ctypes.c_float), ("seq_len", ctypes.c_void_p), ("dropout_p", ctypes.c_float),
+                ("dropout_seed", ctypes.c_uint32)]
 
 
 class BptLayerParams(ctypes.Structure):
@@ -185,7 +186,8 @@ def bpt_build_graph(n: int, k: int, causal: bool) -> Graph:
     return Graph(n, k, causal)
 
 
-def _shape_of(g: Graph, x: torch.Tensor, scale: Optional[float], seq_len: Optional[torch.Tensor] = None) -> BptShape:
+def _shape_of(g: Graph, x: torch.Tensor, scale: Optional[float], seq_len: Optional[torch.Tensor] = None,
+              dropout: Tuple[float, int] = (0.0, 0)) -> BptShape:
     if x.dim() != 4 or x.shape[2] != g.num_nodes:
         raise ValueError("expected a [B,H,N=%d,D] tensor, got %s" % (g.num_nodes, tuple(x.shape)))
     if x.stride(3) != 1:
@@ -203,7 +205,8 @@ def _shape_of(g: Graph, x: torch.Tensor, scale: Optional[float], seq_len: Option
                 seq_len.device != x.device:
             raise ValueError("seq_len must be a contiguous int32 tensor of B entries on the tensors' device")
         lens = seq_len.data_ptr()
-    return BptShape(B, H, D, dt, x.stride(0), x.stride(1), x.stride(2), float(scale) if scale else 0.0, lens)
+    return BptShape(B, H, D, dt, x.stride(0), x.stride(1), x.stride(2), float(scale) if scale else 0.0, lens,
+                    float(dropout[0]), int(dropout[1]) & 0xFFFFFFFF)
 
 
 def _same_layout(ref: torch.Tensor, *others: torch.Tensor) -> None:
@@ -222,11 +225,12 @@ def _workspace(nbytes: int, device) -> Tuple[Optional[torch.Tensor], int]:
 def bpt_attn_fwd(g: Graph, Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, rel: torch.Tensor,
                  scale: Optional[float] = None, out: Optional[torch.Tensor] = None,
                  lse: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
-                 seq_len: Optional[torch.Tensor] = None):
+                 seq_len: Optional[torch.Tensor] = None, dropout: Tuple[float, int] = (0.0, 0)):
     """out, lse = graph attention of eq. (8).  Q,K,V: [B,H,N,D] cuda tensors; rel: [levels,W,D];
-    seq_len: optional int32 [B] token counts of sequences shorter than n."""
+    seq_len: optional int32 [B] token counts of sequences shorter than n; dropout: (rate, seed) of the dropout on
+    the attention weights."""
     L = load_library()
-    shp = _shape_of(g, Q, scale, seq_len)
+    shp = _shape_of(g, Q, scale, seq_len, dropout)
     _same_layout(Q, K, V)
     if K.dtype != Q.dtype or V.dtype != Q.dtype or rel.dtype != Q.dtype:
         raise ValueError("Q, K, V and rel must share a dtype")
@@ -248,9 +252,9 @@ def bpt_attn_fwd(g: Graph, Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, re
     return out, lse
 
 
-def _bwd_prepare(g, Q, K, V, rel, lse, dout, scale, grads, workspace, seq_len=None):
+def _bwd_prepare(g, Q, K, V, rel, lse, dout, scale, grads, workspace, seq_len=None, dropout=(0.0, 0)):
     L = load_library()
-    shp = _shape_of(g, Q, scale, seq_len)
+    shp = _shape_of(g, Q, scale, seq_len, dropout)
     _same_layout(Q, K, V, dout)
     if lse.dtype != torch.float32 or tuple(lse.shape) != tuple(Q.shape[:3]) or not lse.is_contiguous():
         raise ValueError("lse must be contiguous fp32 [B,H,N]")
@@ -270,10 +274,10 @@ def _bwd_prepare(g, Q, K, V, rel, lse, dout, scale, grads, workspace, seq_len=No
 
 def bpt_attn_bwd(g: Graph, Q, K, V, rel, lse, dout, scale: Optional[float] = None,
                  grads: Optional[Tuple[torch.Tensor, ...]] = None, workspace: Optional[torch.Tensor] = None,
-                 seq_len: Optional[torch.Tensor] = None):
-    """dQ, dK, dV, d_rel (all fp32) = gradient of eq. (8) given dout and the forward's lse."""
+                 seq_len: Optional[torch.Tensor] = None, dropout: Tuple[float, int] = (0.0, 0)):
+    """dQ, dK, dV, d_rel (all fp32) = gradient of eq. (8) given dout and the forward's lse (and its dropout)."""
     L, shp, (dQ, dK, dV, d_rel), ws, ws_bytes = _bwd_prepare(g, Q, K, V, rel, lse, dout, scale, grads, workspace,
-                                                             seq_len)
+                                                             seq_len, dropout)
     _check(L.bpt_attn_bwd(g.handle, ctypes.byref(shp), Q.data_ptr(), K.data_ptr(), V.data_ptr(), rel.data_ptr(),
                           lse.data_ptr(), dout.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(),
                           d_rel.data_ptr(), ws.data_ptr(), ws_bytes, _stream_ptr()), "bpt_attn_bwd")
@@ -348,10 +352,10 @@ class GraphAttentionFunction(torch.autograd.Function):
     in fp32 and are cast to the dtype of their inputs."""
 
     @staticmethod
-    def forward(ctx, g, Q, K, V, rel, scale, seq_len):
-        out, lse = bpt_attn_fwd(g, Q, K, V, rel, scale=scale, seq_len=seq_len)
+    def forward(ctx, g, Q, K, V, rel, scale, seq_len, dropout):
+        out, lse = bpt_attn_fwd(g, Q, K, V, rel, scale=scale, seq_len=seq_len, dropout=dropout)
         ctx.save_for_backward(Q, K, V, rel, lse)
-        ctx.g, ctx.scale, ctx.seq_len = g, scale, seq_len
+        ctx.g, ctx.scale, ctx.seq_len, ctx.dropout = g, scale, seq_len, dropout
         return out
 
     @staticmethod
@@ -359,13 +363,16 @@ class GraphAttentionFunction(torch.autograd.Function):
         Q, K, V, rel, lse = ctx.saved_tensors
         if dout.stride() != Q.stride():
             dout = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device).copy_(dout)
-        dQ, dK, dV, d_rel = bpt_attn_bwd(ctx.g, Q, K, V, rel, lse, dout.to(Q.dtype), scale=ctx.scale, seq_len=ctx.seq_len)
-        return None, dQ.to(Q.dtype), dK.to(K.dtype), dV.to(V.dtype), d_rel.to(rel.dtype), None, None
+        dQ, dK, dV, d_rel = bpt_attn_bwd(ctx.g, Q, K, V, rel, lse, dout.to(Q.dtype), scale=ctx.scale, seq_len=ctx.seq_len,
+                                         dropout=ctx.dropout)
+        return None, dQ.to(Q.dtype), dK.to(K.dtype), dV.to(V.dtype), d_rel.to(rel.dtype), None, None, None
 
 
-def graph_attention(g: Graph, Q, K, V, rel, scale: Optional[float] = None, seq_len: Optional[torch.Tensor] = None):
-    """out = graph self-attention of eq. (8), differentiable with respect to Q, K, V and rel."""
-    return GraphAttentionFunction.apply(g, Q, K, V, rel, scale, seq_len)
+def graph_attention(g: Graph, Q, K, V, rel, scale: Optional[float] = None, seq_len: Optional[torch.Tensor] = None,
+                    dropout: Tuple[float, int] = (0.0, 0)):
+    """out = graph self-attention of eq. (8), differentiable with respect to Q, K, V and rel; dropout = (rate, seed)
+    of the dropout on the attention weights (give every call of a training step its own seed)."""
+    return GraphAttentionFunction.apply(g, Q, K, V, rel, scale, seq_len, dropout)
 
 
 def bpt_profile_enable(on: bool) -> None:

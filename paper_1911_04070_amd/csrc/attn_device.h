@@ -44,7 +44,36 @@ struct AttnArgs {
     int32_t rel_rows;       // rows of the whole table
     const int32_t* seq_len; // [B] tokens of every sequence, or null: all have n_tokens
     int32_t lg;             // log2(n_tokens)
+    // dropout on the attention weights: an edge is kept iff its hash >= drop_thr (0: no dropout)
+    uint32_t drop_thr, drop_seed;
+    float drop_inv_keep;    // 1 / (1 - p)
 };
+
+// ---- dropout on the attention weights ---------------------------------------------------
+// Inverted dropout after the softmax (the p_a of the paper's hyper-parameter tables): the weight
+// of a kept edge is multiplied by 1/(1-p), that of a dropped one by 0, in the weighted sum of
+// values; lse stays that of the full softmax.  The mask is a counter-based hash of (seed,
+// batch*heads index, query node, x) with x = relative-position id of the edge for a token row
+// and 2^31 + key node for a span row -- both name the edge within its row, and every kernel
+// that meets the edge (forward, query side, key side) can form them:
+//   keep = mix(mix(mix(seed ^ 0x9E3779B9 * bh) + u) + x) >= floor(p * 2^32).
+__device__ __forceinline__ uint32_t mix32(uint32_t z) {
+    z ^= z >> 16;
+    z *= 0x7FEB352Du;
+    z ^= z >> 15;
+    z *= 0x846CA68Bu;
+    z ^= z >> 16;
+    return z;
+}
+__device__ __forceinline__ uint32_t drop_bh_hash(uint32_t seed, int bh) { return mix32(seed ^ (0x9E3779B9u * (uint32_t)bh)); }
+__device__ __forceinline__ uint32_t drop_row_hash(uint32_t bh_hash, int u) { return mix32(bh_hash + (uint32_t)u); }
+__device__ __forceinline__ uint32_t drop_edge_x(bool token_row, int rel_id, int key_node) {
+    return token_row ? (uint32_t)rel_id : 0x80000000u + (uint32_t)key_node;
+}
+// multiplier of the edge's weight: 1/(1-p) or 0 (thr == 0: always inv_keep == 1)
+__device__ __forceinline__ float drop_scale(uint32_t row_hash, uint32_t x, uint32_t thr, float inv_keep) {
+    return mix32(row_hash + x) >= thr ? inv_keep : 0.f;
+}
 
 // ---- wave-uniform loads of read-only tables -------------------------------------------
 // Graph metadata and sequence lengths are written by no attention kernel, and the tile kernels

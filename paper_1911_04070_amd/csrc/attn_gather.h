@@ -35,6 +35,7 @@ __device__ __forceinline__ void fwd_segment(const AttnArgs& a, const T* rel_s, r
     const int lane_off = sub * 8 * (int)sizeof(T);
     const T* relg = static_cast<const T*>(a.rel) + sub * 8;
     const bool row_kept = node_first_token(u, a.lg) < len;
+    const uint32_t rowh = drop_row_hash(drop_bh_hash(a.drop_seed, bh), u);
 
     // indices two iterations ahead, rows one iteration ahead.  Lanes past the end of
     // the segment read the next rows' indices (or 0 past the array): valid nodes,
@@ -71,6 +72,7 @@ __device__ __forceinline__ void fwd_segment(const AttnArgs& a, const T* rel_s, r
         eo += 32;
 
         const bool valid = eb + slot < e1 && row_kept && node_first_token(cnow, a.lg) < len;
+        const float keep = a.drop_thr ? drop_scale(rowh, drop_edge_x(!SPAN, r0, cnow), a.drop_thr, a.drop_inv_keep) : 1.f;
         cnow = c1;
         float vv[8], d = 0.f;
         if (!SPAN) {
@@ -89,10 +91,11 @@ __device__ __forceinline__ void fwd_segment(const AttnArgs& a, const T* rel_s, r
         unpack(vc, vv);
         l *= corr;
         l += p;
+        const float pk = p * keep;   // dropout acts on the weighted sum only
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             acc[i] *= corr;
-            acc[i] = fmaf(p, vv[i], acc[i]);
+            acc[i] = fmaf(pk, vv[i], acc[i]);
         }
         c1 = c2;
         r0 = r1;
@@ -142,6 +145,7 @@ __device__ __forceinline__ void fwd_span8(const AttnArgs& a, rsrc_t rK, rsrc_t r
     const float qscale = a.scale * kLog2e;
     const float shift =
         sum8(dot8(q, load_row(static_cast<const T*>(a.rel) + (int64_t)a.ib[e0] * kD + sub * 8), 0.f)) * qscale;
+    const uint32_t rowh = drop_row_hash(drop_bh_hash(a.drop_seed, bh), u);
     float m = kNegBig, l = 0.f, acc[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] = 0.f;
@@ -159,10 +163,11 @@ __device__ __forceinline__ void fwd_span8(const AttnArgs& a, rsrc_t rK, rsrc_t r
         unpack(vc, vv);
         l *= corr;
         l += p;
+        const float pk = a.drop_thr ? p * drop_scale(rowh, drop_edge_x(false, 0, tok0 + i), a.drop_thr, a.drop_inv_keep) : p;
 #pragma unroll
         for (int x = 0; x < 8; ++x) {
             acc[x] *= corr;
-            acc[x] = fmaf(p, vv[x], acc[x]);
+            acc[x] = fmaf(pk, vv[x], acc[x]);
         }
     };
     Row<T> k1, v1;
@@ -250,6 +255,7 @@ __device__ __forceinline__ void bwd_q_segment(const AttnArgs& a, const T* rel_s,
     const int lane_off = sub * 8 * (int)sizeof(T);
     const T* relg = static_cast<const T*>(a.rel) + sub * 8;
     const bool row_kept = node_first_token(u, a.lg) < len;
+    const uint32_t rowh = drop_row_hash(drop_bh_hash(a.drop_seed, bh), u);
 
     int eo = (e0 + slot) * 4;
     const int c0 = buf_i32(rIa, eo);
@@ -290,6 +296,7 @@ __device__ __forceinline__ void bwd_q_segment(const AttnArgs& a, const T* rel_s,
 
         const bool inside = eb + slot < e1;
         const bool valid = inside && row_kept && node_first_token(cnow, a.lg) < len;
+        const float keep = a.drop_thr ? drop_scale(rowh, drop_edge_x(!SPAN, r0, cnow), a.drop_thr, a.drop_inv_keep) : 1.f;
         cnow = c1;
         float kk[8];
         unpack(kc, kk);
@@ -307,7 +314,7 @@ __device__ __forceinline__ void bwd_q_segment(const AttnArgs& a, const T* rel_s,
 #pragma unroll
         for (int i = 0; i < 8; ++i) d += qs[i] * kk[i];
         const float sc = sum8(d) + shift;
-        const float dP = sum8(dot8(g, vc, 0.f));
+        const float dP = sum8(dot8(g, vc, 0.f)) * keep;   // out = sum keep p v: dP carries the mask
         const float p = valid ? fast_exp2(sc - lse2) : 0.f;
         const float wgt = p * dP;
         dl += wgt;
@@ -360,6 +367,7 @@ __device__ __forceinline__ void bwd_q_span8(const AttnArgs& a, rsrc_t rK, rsrc_t
 #pragma unroll
     for (int i = 0; i < 8; ++i) qs[i] *= qscale;
     const float lse2 = a.lse_r[(int64_t)bh * a.N + u] * kLog2e;
+    const uint32_t rowh = drop_row_hash(drop_bh_hash(a.drop_seed, bh), u);
     float shift;
     {
         float r[8], d = 0.f;
@@ -380,7 +388,8 @@ __device__ __forceinline__ void bwd_q_span8(const AttnArgs& a, rsrc_t rK, rsrc_t
 #pragma unroll
         for (int x = 0; x < 8; ++x) d += qs[x] * kk[x];
         const float p = tok0 + i < len ? fast_exp2(sum8(d) + shift - lse2) : 0.f;
-        const float wgt = p * sum8(dot8(g, vc, 0.f));
+        const float keep = a.drop_thr ? drop_scale(rowh, drop_edge_x(false, 0, tok0 + i), a.drop_thr, a.drop_inv_keep) : 1.f;
+        const float wgt = p * sum8(dot8(g, vc, 0.f)) * keep;
         dl += wgt;
 #pragma unroll
         for (int x = 0; x < 8; ++x) {
@@ -476,6 +485,8 @@ __device__ __forceinline__ void bwd_kv_segment(const AttnArgs& a, const T* rel_s
     if (e1 > e0 && node_first_token(v, a.lg) < len) {
         int eo = (e0 + slot) * 4;
         const int u0 = buf_i32(rIa, eo);
+        int unow = u0;   // query node of the rows in work
+        const uint32_t bhh = drop_bh_hash(a.drop_seed, bh);
         int u1 = buf_i32(rIa, eo + 32);
         int r0 = buf_i32(rIb, eo), r1 = buf_i32(rIb, eo + 32);
         Row<T> q0 = gather_row<T>(rQ, u0, a.row_bytes, lane_off), g0 = gather_row<T>(rG, u0, a.row_bytes, lane_off);
@@ -497,15 +508,20 @@ __device__ __forceinline__ void bwd_kv_segment(const AttnArgs& a, const T* rel_s
             float d = dot8(qc, REL_LDS ? load_row(rel_s + r0 * kD + sub * 8) : load_row(relg + (int64_t)r0 * kD), 0.f);
             d = dot8(qc, kk, d);
             const float sc = sum8(d) * qscale;
-            const float dP = sum8(dot8(gc, vv, 0.f));
+            const float keep = a.drop_thr ? drop_scale(drop_row_hash(bhh, unow), drop_edge_x(unow < a.n_tokens, r0, v), a.drop_thr,
+                                                       a.drop_inv_keep)
+                                          : 1.f;
+            unow = u1;
+            const float dP = sum8(dot8(gc, vv, 0.f)) * keep;
             unpack(qc, q);
             unpack(gc, g);
             const float p = valid ? fast_exp2(sc - stc.x) : 0.f;
             const float dS = p * (dP - stc.y);
+            const float pk = p * keep;
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 dk[i] = fmaf(dS, q[i], dk[i]);
-                dv[i] = fmaf(p, g[i], dv[i]);
+                dv[i] = fmaf(pk, g[i], dv[i]);
             }
             u1 = u2;
             r0 = r1;

@@ -4,6 +4,7 @@
 // kernels over dense tiles (attn_token_tiles.h, attn_span_tiles.h, attn_key_tiles.h: bf16),
 // lays out the workspace, launches, and exports the C entry points of bpt.h.
 #include <algorithm>
+#include <cmath>
 
 #include "attn_device.h"
 #include "attn_gather.h"
@@ -44,6 +45,7 @@ int check_shape(const bpt_graph* g, const bpt_shape_t* s) {
     if (s->dtype != BPT_F32 && s->dtype != BPT_BF16) return BPT_ERR_UNSUPPORTED;
     if (s->stride_n < kD || (s->stride_n % 8) || (s->stride_h % 8) || (s->stride_b % 8)) return BPT_ERR_INVALID_ARG;
     if (s->stride_h < 0 || s->stride_b < 0) return BPT_ERR_INVALID_ARG;
+    if (!(s->dropout_p >= 0.f && s->dropout_p < 1.f)) return BPT_ERR_INVALID_ARG;
     if ((int64_t)s->B * s->H > (int64_t)INT32_MAX / std::max(g->fwd.num_tiles, g->tr.num_tiles))
         return BPT_ERR_UNSUPPORTED;
     if ((int64_t)s->B * s->H * g->num_nodes > (int64_t)1 << 40) return BPT_ERR_UNSUPPORTED;
@@ -120,6 +122,10 @@ void fill_common(AttnArgs& a, const bpt_graph* g, const bpt_shape_t* s) {
     a.idx_bytes = (uint32_t)(g->num_edges * 4);
     a.seq_len = s->seq_len;
     a.lg = g->num_levels - 1;
+    const double p = s->dropout_p > 0.f ? (double)s->dropout_p : 0.0;
+    a.drop_thr = p > 0.0 ? (uint32_t)std::min(std::floor(p * 4294967296.0), 4294967295.0) : 0u;
+    a.drop_seed = s->dropout_seed;
+    a.drop_inv_keep = p > 0.0 ? (float)(1.0 / (1.0 - p)) : 1.f;
 }
 
 void use_schedule(AttnArgs& a, const Schedule& sc) {
@@ -297,7 +303,7 @@ int run_fwd(const bpt_graph* g, AttnArgs& a, hipStream_t st) {
     if (rc) return rc;
     if (sizeof(T) == 2) {
         const TilePlan tp = plan_tiles(g, lim);
-        if (tp.ok) {
+        if (tp.ok && a.drop_thr == 0) {   // dropout runs on the gather kernels
             if ((rc = run_fwd_tiles(g, a, lim, tp, st))) return rc;
             if (span_tiles_ok(g)) return run_span_tiles(g, a, true, st);
             use_schedule(a, g->fwd_span);  // the gather kernel below only sees span rows
@@ -356,13 +362,14 @@ int plan_bwd(const bpt_graph* g, const bpt_shape_t* s, BwdPlan* p) {
         // dense tiles for the query side: when one workgroup of the d_rel kernel can hold all ids in use
         const int cids = (g->tiles.num_cids + 31) & ~31;
         const size_t rg_lds = ((size_t)2 * cids * kRgStride + kRgRows * kRowStride + (size_t)cids * kRelStride) * sizeof(bf16_t);
-        if (plan_tiles(g, lim).ok && cids <= kRgTileMaxIds && rg_lds + 256 <= lim.lds) {
+        const bool dropout = s->dropout_p > 0.f;   // the mask is formed by the gather kernels only
+        if (!dropout && plan_tiles(g, lim).ok && cids <= kRgTileMaxIds && rg_lds + 256 <= lim.lds) {
             p->q_tiles = true;
             p->drel_tile = true;
             p->drel_part_rows = cids;
             p->drel_lds = rg_lds;
         }
-        if (g->ktiles.num_tasks > 0 && g->ktiles.nb_pad <= 16 * kMaxBiasChunks) {
+        if (!dropout && g->ktiles.num_tasks > 0 && g->ktiles.nb_pad <= 16 * kMaxBiasChunks) {
             const int parked = std::max(0, g->ktiles.nb_pad / 16 - kRegBiasChunks);   // table operands kept in LDS
             p->kv_lds = (size_t)kTileWaves * (32 * (g->ktiles.nb_pad + 1) * sizeof(float) + 64 * kRowStride * sizeof(bf16_t) +
                                               32 * sizeof(float2) + (size_t)parked * 64 * 32);

@@ -305,6 +305,43 @@ def test_random_small_configurations():
             run_case(w)
 
 
+DROPOUT = [
+    ("f32", 64, 2, False, 2, 2, 0.1, None), ("f32", 256, 3, True, 1, 2, 0.5, None),
+    ("bf16", 512, 4, False, 2, 2, 0.1, None), ("bf16", 2048, 8, True, 1, 2, 0.3, None),
+    ("bf16", 1024, 5, False, 2, 1, 0.2, [1000, 300]), ("bf16", 4096, 40, False, 1, 1, 0.1, None),
+]
+
+
+@pytest.mark.parametrize("dtype,n,k,causal,B,H,p,lengths", DROPOUT)
+def test_dropout_on_attention_weights(dtype, n, k, causal, B, H, p, lengths):
+    # the same counter-based mask on both sides: an edge is dropped on the GPU iff the oracle drops it
+    say("dropout", dtype, n, k, causal, B, H, p, lengths)
+    w = Workload("dropout", 25, n, k, causal, B, H, 64, dtype, True)
+    seed = 20191104 + n
+    x = make_inputs(w)
+    g = bpt.bpt_build_graph(n, k, causal)
+    Q, K, V, dO, R = (to_dev(x[k_], dtype) for k_ in ("Q", "K", "V", "dO", "Rel"))
+    lens = lengths if lengths is not None else [n] * B
+    lens_d = torch.tensor(lens, dtype=torch.int32, device="cuda") if lengths is not None else None
+    out_d, lse_d = bpt.bpt_attn_fwd(g, Q, K, V, R, scale=w.scale, seq_len=lens_d, dropout=(p, seed))
+    grads = bpt.bpt_attn_bwd(g, Q, K, V, R, lse_d, dO, scale=w.scale, seq_len=lens_d, dropout=(p, seed))
+    torch.cuda.synchronize()
+    o, l, _ = oracle.attn_fwd_lengths(n, k, causal, lens, x["Q"], x["K"], x["V"], x["Rel"], w.scale, dropout=p, seed=seed)
+    refs = oracle.attn_bwd_lengths(n, k, causal, lens, x["Q"], x["K"], x["V"], x["Rel"], x["dO"], w.scale, dropout=p,
+                                   seed=seed)
+    res = {}
+    for name, got_t, ref in zip(("out", "lse", "dQ", "dK", "dV", "d_rel"), (out_d, lse_d) + tuple(grads), (o, l) + refs):
+        got = host(got_t)
+        assert np.isfinite(got).all(), name
+        res[name] = float(np.abs(got - ref).max())
+        assert res[name] <= TOL[dtype], (name, res[name])
+    # and it is a different result from the one without dropout
+    out0, _ = bpt.bpt_attn_fwd(g, Q, K, V, R, scale=w.scale, seq_len=lens_d)
+    assert float((out0.float() - out_d.float()).abs().max()) > 0.05
+    say("   max-abs errors", {k_: float("%.3g" % v) for k_, v in res.items()})
+    g.destroy()
+
+
 def test_autograd_function_returns_the_library_gradients():
     w = Workload("autograd", 24, 256, 3, False, 2, 2, 64, "f32", True)
     x = make_inputs(w)
