@@ -46,6 +46,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="lm")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--dropout", type=float, default=0.0,
+                    help="dropout rate on the attention weights (the mask is formed inside the kernels); 0 = the "
+                         "headline configuration")
     ap.add_argument("--layer", action="store_true",
                     help="time the forward of one whole graph layer (projections, attention, FFN, normalisations; "
                          "d_ff = 4 d) of the workload's shape instead of the attention path")
@@ -164,10 +167,13 @@ def main():
     ws_f = torch.empty(max(fws, 256), dtype=torch.uint8, device="cuda")
     ws_b = torch.empty(max(bws, 256), dtype=torch.uint8, device="cuda")
 
+    drop = (args.dropout, 1911) if args.dropout > 0 else None
+
     def step():
-        bpt.bpt_attn_fwd(g, Q, K, V, R, scale=w.scale, out=out, lse=lse, workspace=ws_f, seq_len=lens_d)
+        bpt.bpt_attn_fwd(g, Q, K, V, R, scale=w.scale, out=out, lse=lse, workspace=ws_f, seq_len=lens_d, dropout=drop)
         if w.backward:
-            bpt.bpt_attn_bwd(g, Q, K, V, R, lse, dO, scale=w.scale, grads=grads, workspace=ws_b, seq_len=lens_d)
+            bpt.bpt_attn_bwd(g, Q, K, V, R, lse, dO, scale=w.scale, grads=grads, workspace=ws_b, seq_len=lens_d,
+                             dropout=drop)
 
     for _ in range(args.warmup):
         step()
@@ -190,14 +196,14 @@ def main():
 
     reps = max(5, min(args.steps, 30))
     stage_ms = {"fwd": timed(lambda: bpt.bpt_attn_fwd(g, Q, K, V, R, scale=w.scale, out=out, lse=lse,
-                                                      workspace=ws_f, seq_len=lens_d), reps)}
+                                                      workspace=ws_f, seq_len=lens_d, dropout=drop), reps)}
     if w.backward:
         stage_ms["bwd_query_side"] = timed(
             lambda: bpt.bpt_attn_bwd_query_side(g, Q, K, V, R, lse, dO, grads[0], grads[3], ws_b, scale=w.scale,
-                                                seq_len=lens_d), reps)
+                                                seq_len=lens_d, dropout=drop), reps)
         stage_ms["bwd_key_side"] = timed(
             lambda: bpt.bpt_attn_bwd_key_side(g, Q, K, V, R, lse, dO, grads[1], grads[2], ws_b, scale=w.scale,
-                                              seq_len=lens_d), reps)
+                                              seq_len=lens_d, dropout=drop), reps)
 
     # per-kernel device time, live: the library brackets each of its launches with HIP events on the launch stream
     bpt.bpt_profile_enable(True)
@@ -288,7 +294,7 @@ def main():
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "n": w.n, "k": w.k, "causal": w.causal, "batch": w.B, "heads": w.H,
                    "head_dim": w.D, "nodes": g.num_nodes, "edges": g.num_edges, "edge_instances": edge_inst,
-                   "backward": w.backward,
+                   "backward": w.backward, "dropout": args.dropout,
                    "lengths": ([int(v) for v in lengths] if lengths is not None else None)},
         "graph_build_ms": round(build_ms, 3),
         "edges_per_s_incl_build": round(edge_inst / ((ms_per_step + build_ms) * 1e-3), 1),

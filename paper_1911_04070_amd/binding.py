@@ -187,7 +187,7 @@ def bpt_build_graph(n: int, k: int, causal: bool) -> Graph:
 
 
 def _shape_of(g: Graph, x: torch.Tensor, scale: Optional[float], seq_len: Optional[torch.Tensor] = None,
-              dropout: Tuple[float, int] = (0.0, 0)) -> BptShape:
+              dropout: Optional[Tuple[float, int]] = None) -> BptShape:
     if x.dim() != 4 or x.shape[2] != g.num_nodes:
         raise ValueError("expected a [B,H,N=%d,D] tensor, got %s" % (g.num_nodes, tuple(x.shape)))
     if x.stride(3) != 1:
@@ -206,7 +206,7 @@ def _shape_of(g: Graph, x: torch.Tensor, scale: Optional[float], seq_len: Option
             raise ValueError("seq_len must be a contiguous int32 tensor of B entries on the tensors' device")
         lens = seq_len.data_ptr()
     return BptShape(B, H, D, dt, x.stride(0), x.stride(1), x.stride(2), float(scale) if scale else 0.0, lens,
-                    float(dropout[0]), int(dropout[1]) & 0xFFFFFFFF)
+                    float(dropout[0]) if dropout else 0.0, (int(dropout[1]) & 0xFFFFFFFF) if dropout else 0)
 
 
 def _same_layout(ref: torch.Tensor, *others: torch.Tensor) -> None:
@@ -225,7 +225,7 @@ def _workspace(nbytes: int, device) -> Tuple[Optional[torch.Tensor], int]:
 def bpt_attn_fwd(g: Graph, Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, rel: torch.Tensor,
                  scale: Optional[float] = None, out: Optional[torch.Tensor] = None,
                  lse: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
-                 seq_len: Optional[torch.Tensor] = None, dropout: Tuple[float, int] = (0.0, 0)):
+                 seq_len: Optional[torch.Tensor] = None, dropout: Optional[Tuple[float, int]] = None):
     """out, lse = graph attention of eq. (8).  Q,K,V: [B,H,N,D] cuda tensors; rel: [levels,W,D];
     seq_len: optional int32 [B] token counts of sequences shorter than n; dropout: (rate, seed) of the dropout on
     the attention weights."""
@@ -252,7 +252,7 @@ def bpt_attn_fwd(g: Graph, Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, re
     return out, lse
 
 
-def _bwd_prepare(g, Q, K, V, rel, lse, dout, scale, grads, workspace, seq_len=None, dropout=(0.0, 0)):
+def _bwd_prepare(g, Q, K, V, rel, lse, dout, scale, grads, workspace, seq_len=None, dropout=None):
     L = load_library()
     shp = _shape_of(g, Q, scale, seq_len, dropout)
     _same_layout(Q, K, V, dout)
@@ -274,7 +274,7 @@ def _bwd_prepare(g, Q, K, V, rel, lse, dout, scale, grads, workspace, seq_len=No
 
 def bpt_attn_bwd(g: Graph, Q, K, V, rel, lse, dout, scale: Optional[float] = None,
                  grads: Optional[Tuple[torch.Tensor, ...]] = None, workspace: Optional[torch.Tensor] = None,
-                 seq_len: Optional[torch.Tensor] = None, dropout: Tuple[float, int] = (0.0, 0)):
+                 seq_len: Optional[torch.Tensor] = None, dropout: Optional[Tuple[float, int]] = None):
     """dQ, dK, dV, d_rel (all fp32) = gradient of eq. (8) given dout and the forward's lse (and its dropout)."""
     L, shp, (dQ, dK, dV, d_rel), ws, ws_bytes = _bwd_prepare(g, Q, K, V, rel, lse, dout, scale, grads, workspace,
                                                              seq_len, dropout)
@@ -285,10 +285,11 @@ def bpt_attn_bwd(g: Graph, Q, K, V, rel, lse, dout, scale: Optional[float] = Non
 
 
 def bpt_attn_bwd_query_side(g: Graph, Q, K, V, rel, lse, dout, dQ, d_rel, workspace,
-                            scale: Optional[float] = None, seq_len: Optional[torch.Tensor] = None):
+                            scale: Optional[float] = None, seq_len: Optional[torch.Tensor] = None,
+                            dropout: Optional[Tuple[float, int]] = None):
     """First stage of the backward: dQ, d_rel, and delta into the workspace."""
     L = load_library()
-    shp = _shape_of(g, Q, scale, seq_len)
+    shp = _shape_of(g, Q, scale, seq_len, dropout)
     _check(L.bpt_attn_bwd_query_side(g.handle, ctypes.byref(shp), Q.data_ptr(), K.data_ptr(), V.data_ptr(),
                                      rel.data_ptr(), lse.data_ptr(), dout.data_ptr(), dQ.data_ptr(),
                                      d_rel.data_ptr(), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
@@ -297,10 +298,10 @@ def bpt_attn_bwd_query_side(g: Graph, Q, K, V, rel, lse, dout, dQ, d_rel, worksp
 
 
 def bpt_attn_bwd_key_side(g: Graph, Q, K, V, rel, lse, dout, dK, dV, workspace, scale: Optional[float] = None,
-                          seq_len: Optional[torch.Tensor] = None):
+                          seq_len: Optional[torch.Tensor] = None, dropout: Optional[Tuple[float, int]] = None):
     """Second stage of the backward: dK, dV (reads delta from the workspace)."""
     L = load_library()
-    shp = _shape_of(g, Q, scale, seq_len)
+    shp = _shape_of(g, Q, scale, seq_len, dropout)
     _check(L.bpt_attn_bwd_key_side(g.handle, ctypes.byref(shp), Q.data_ptr(), K.data_ptr(), V.data_ptr(),
                                    rel.data_ptr(), lse.data_ptr(), dout.data_ptr(), dK.data_ptr(), dV.data_ptr(),
                                    workspace.data_ptr(),
@@ -369,7 +370,7 @@ class GraphAttentionFunction(torch.autograd.Function):
 
 
 def graph_attention(g: Graph, Q, K, V, rel, scale: Optional[float] = None, seq_len: Optional[torch.Tensor] = None,
-                    dropout: Tuple[float, int] = (0.0, 0)):
+                    dropout: Optional[Tuple[float, int]] = None):
     """out = graph self-attention of eq. (8), differentiable with respect to Q, K, V and rel; dropout = (rate, seed)
     of the dropout on the attention weights (give every call of a training step its own seed)."""
     return GraphAttentionFunction.apply(g, Q, K, V, rel, scale, seq_len, dropout)

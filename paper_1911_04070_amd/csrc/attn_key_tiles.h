@@ -36,9 +36,11 @@ struct KeyArgs {
     int32_t num_tasks, num_part, num_chunks, nb_pad, W, zero;
     const int32_t* seq_len;   // [B] tokens of every sequence, or null
     int32_t n;
+    uint32_t drop_thr, drop_seed;   // dropout on the attention weights (DROP variants)
+    float drop_inv_keep;
 };
 
-template <int NBC>
+template <int NBC, bool DROP>
 __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int lane = threadIdx.x & 63;
@@ -55,8 +57,14 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyA
                      (size_t)wave * 32;                                                          // [32 queries] (lse, delta)
     // table operands beyond the kRegBiasChunks kept in registers: every lane parks and re-reads its own 32 bytes
     constexpr int kParked = NBC > kRegBiasChunks ? NBC - kRegBiasChunks : 0;
+    // DROP: hash of (seed, batch*head, query node) of the 32 queries, what the mask of their edges is drawn from
+    uint32_t* rowh_s = reinterpret_cast<uint32_t*>(smem + (size_t)kTileWaves * (32 * bstride * sizeof(float) +
+                                                                                64 * kRowStride * sizeof(bf16_t) +
+                                                                                32 * sizeof(float2))) +
+                       (size_t)wave * 32;
     uint4* rb_s = reinterpret_cast<uint4*>(smem + (size_t)kTileWaves * (32 * bstride * sizeof(float) +
-                                                                        64 * kRowStride * sizeof(bf16_t) + 32 * sizeof(float2))) +
+                                                                        64 * kRowStride * sizeof(bf16_t) + 32 * sizeof(float2) +
+                                                                        32 * sizeof(uint32_t))) +
                   ((size_t)wave * (kParked > 0 ? kParked : 1) * 64 + lane) * 2;
     const float qscale = a.scale * kLog2e;
     const int groups = (a.num_tasks + kTileWaves - 1) / kTileWaves;
@@ -105,6 +113,8 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyA
         // into the operand layouts of the matrix instructions.
         Row<bf16_t> qa[2][2], ga[2][2];
         float2 stn[2][2];   // (lse, delta) of the row, kept by the lane that fetches its first piece
+        uint32_t rhn[2][2];  // DROP: the row's hash
+        const uint32_t bhh = DROP ? drop_bh_hash(a.drop_seed, bh) : 0u;
         auto load_rows = [&]() {
 #pragma unroll
             for (int ci = 0; ci < 2; ++ci)
@@ -114,6 +124,7 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyA
                     buf_row(rQ, off, qa[ci][h]);
                     buf_row(rG, off, ga[ci][h]);
                     stn[ci][h] = buf_f2(rS, node[ci][h] * 8);
+                    if (DROP) rhn[ci][h] = drop_row_hash(bhh, node[ci][h]);
                 }
         };
         load_idx(0);
@@ -161,6 +172,7 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyA
                     *reinterpret_cast<uint4*>(q_s + row * kRowStride + piece * 8) = qa[ci][h].w;
                     *reinterpret_cast<uint4*>(g_s + row * kRowStride + piece * 8) = ga[ci][h].w;
                     if (piece == 0) stat_s[row] = stn[ci][h];
+                    if (DROP && piece == 0) rowh_s[row] = rhn[ci][h];
                 }
             __builtin_amdgcn_sched_barrier(0);
             // the row registers are free: request the next pair's rows, then the ids of the pair after it
@@ -231,8 +243,17 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyA
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const float p = bid[ci][r] >= 0 && key_kept ? fast_exp2((s4[ci][r] + bv[ci][r]) * qscale - st[ci][r].x) : 0.f;
-                    pp[ci][r] = p;
-                    ds[ci][r] = p * (d4[ci][r] - st[ci][r].y);
+                    if (DROP) {
+                        // a token row's edge is named by its relative-position id, a span row's by the key node;
+                        // out = sum keep p v: dV takes keep p, and dP carries the mask into dS
+                        const uint32_t x = bid[ci][r] < a.W ? (uint32_t)(level * a.W + bid[ci][r]) : 0x80000000u + (uint32_t)(node0 + j);
+                        const float keep = drop_scale(rowh_s[16 * ci + 4 * g + r], x, a.drop_thr, a.drop_inv_keep);
+                        pp[ci][r] = p * keep;
+                        ds[ci][r] = p * (d4[ci][r] * keep - st[ci][r].y);
+                    } else {
+                        pp[ci][r] = p;
+                        ds[ci][r] = p * (d4[ci][r] - st[ci][r].y);
+                    }
                 }
             // dS and P as A operands, each as bf16 hi + lo: the sums run over up to thousands of
             // queries and the tolerance is absolute, so 8 mantissa bits are not enough

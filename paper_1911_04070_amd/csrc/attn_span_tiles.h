@@ -35,6 +35,8 @@ struct SpanArgs {
     int32_t BH, H, N, n, L, W, zero;
     float scale;
     const int32_t* seq_len;   // [B] tokens of every sequence, or null
+    uint32_t drop_thr, drop_seed;   // dropout on the attention weights (DROP variants)
+    float drop_inv_keep;
 };
 __device__ __forceinline__ int span_level_offset(int n, int level) { return 2 * n - ((2 * n) >> level); }
 // query slot -> (level, index inside the block at that level); group is wave-uniform
@@ -98,6 +100,7 @@ __device__ __forceinline__ void span_block_gone(const SpanArgs& a, int bh, int b
     }
 }
 
+template <bool DROP>
 __global__ void __launch_bounds__(kTileThreads) fwd_span_tile_kernel(const SpanArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int lane = threadIdx.x & 63;
@@ -169,6 +172,14 @@ __global__ void __launch_bounds__(kTileThreads) fwd_span_tile_kernel(const SpanA
             }
         l += __shfl_xor(l, 16);
         l += __shfl_xor(l, 32);
+        if (DROP) {   // the row sum keeps every edge; the weighted sum of values takes the mask of (span node, token)
+            const uint32_t rowh = drop_row_hash(drop_bh_hash(a.drop_seed, bh), node);
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    p[c][r] *= drop_scale(rowh, drop_edge_x(false, 0, t0 + 16 * c + 4 * g + r), a.drop_thr, a.drop_inv_keep);
+        }
         u32x4 pa;
         pa.x = pack_bf16(p[0][0], p[0][1]);
         pa.y = pack_bf16(p[0][2], p[0][3]);
@@ -337,6 +348,7 @@ __global__ void __launch_bounds__(kSpanBigThreads) fwd_span_merge_kernel(const S
 // and dS = w - delta p are final and dQ = scale * dS K_block (r_anc drops out: the dS of a row
 // sum to zero).  An ancestor stores the partial sums A = W K, Bv = P K, delta, which the merge
 // kernel turns into dQ = scale * (sum A - delta * sum Bv).
+template <bool DROP>
 __global__ void __launch_bounds__(kTileThreads, 3) bwd_q_span_tile_kernel(const SpanArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int lane = threadIdx.x & 63;
@@ -390,6 +402,7 @@ __global__ void __launch_bounds__(kTileThreads, 3) bwd_q_span_tile_kernel(const 
         const bf16x8_t gb1 = *reinterpret_cast<const bf16x8_t*>(grow + 8);
         const float lse2 = a.lse_r[(int64_t)bh * a.N + node] * kLog2e;
         const float shift = span_shift(a, level, g, qb0, qb1, qscale);
+        const uint32_t rowh = DROP ? drop_row_hash(drop_bh_hash(a.drop_seed, bh), node) : 0u;
         float p[2][4], wgt[2][4], dl = 0.f;
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
@@ -403,7 +416,8 @@ __global__ void __launch_bounds__(kTileThreads, 3) bwd_q_span_tile_kernel(const 
                 const int tt = 16 * c + 4 * g + r;
                 const bool member = valid && (grp == 2 || (tt >> level) == loc) && t0 + tt < len;
                 p[c][r] = member ? fast_exp2(s4[r] * qscale + shift - lse2) : 0.f;
-                wgt[c][r] = p[c][r] * d4[r];
+                const float keep = DROP ? drop_scale(rowh, drop_edge_x(false, 0, t0 + tt), a.drop_thr, a.drop_inv_keep) : 1.f;
+                wgt[c][r] = p[c][r] * d4[r] * keep;
                 dl += wgt[c][r];
             }
         }

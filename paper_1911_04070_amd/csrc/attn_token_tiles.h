@@ -51,6 +51,9 @@ struct TileArgs {
     // sequences shorter than n
     const int32_t *seq_len, *id_to_cid;
     int32_t n, k, W, ctx_levels, causal;
+    // dropout on the attention weights (DROP variants of the kernels)
+    uint32_t drop_thr, drop_seed;
+    float drop_inv_keep;
 };
 
 __device__ __forceinline__ void wave_lds_sync() {  // order LDS traffic between the lanes of one wavefront
@@ -120,7 +123,7 @@ struct TileCursor {
 
 // REL_LDS: the compact relative-position table is staged in LDS; otherwise (large tables) its rows
 // are read from memory when a tile forms its bias table.
-template <bool REL_LDS>
+template <bool REL_LDS, bool DROP>
 __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     bf16_t* rel_s = reinterpret_cast<bf16_t*>(smem);                                   // [cid_pad][kRelStride]
@@ -134,6 +137,11 @@ __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArg
     bf16_t* k_s = reinterpret_cast<bf16_t*>(smem + rel_bytes + (size_t)kTileWaves * 16 * a.bias_stride * sizeof(float)) +
                   (size_t)wave * 64 * kRowStride;                                       // [32 columns][kRowStride]: K rows
     bf16_t* v_s = k_s + 32 * kRowStride;                                                // the same for V rows
+    // DROP: relative-position id of every compact id, what the dropout mask of an edge is drawn from
+    int32_t* relid_s = reinterpret_cast<int32_t*>(smem + rel_bytes + (size_t)kTileWaves * 16 * a.bias_stride * sizeof(float) +
+                                                  (size_t)kTileWaves * 64 * kRowStride * sizeof(bf16_t));   // [cid_pad]
+    if (DROP)
+        for (int i = threadIdx.x; i < a.cid_pad; i += blockDim.x) relid_s[i] = i < a.num_cids ? a.cid_to_id[i] : 0;
     // compact relative-position table, zero rows as padding
     if (REL_LDS) {
         for (int i = threadIdx.x; i < a.cid_pad * 8; i += blockDim.x) {
@@ -233,9 +241,11 @@ __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArg
     bf16x8_t qb0, qb1;
     float m_run = kNegBig, l_part = 0.f;
     f32x4_t o[4];
+    uint32_t rowh = 0;   // DROP: hash of (seed, batch*head, token j of the tile)
 
     while (cc.valid) {
         if (cc.pair == 0) {   // a new tile: its Q rows arrived with the rows of this pair
+            if (DROP) rowh = drop_row_hash(drop_bh_hash(a.drop_seed, cc.bh), cc.tile * 16 + j);
             qb0 = qn0;
             qb1 = qn1;
             m_run = kNegBig;
@@ -332,6 +342,13 @@ __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArg
                 psum += p;
             }
         l_part = l_part * corr + psum;
+        if (DROP) {   // dropout acts on the weighted sum of values only: the row sum keeps every edge
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    sc[c][r] *= drop_scale(rowh, (uint32_t)relid_s[max(cid[c][r], 0)], a.drop_thr, a.drop_inv_keep);
+        }
         // the accumulators hold tokens 4g..4g+3: fetch their correction factors
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -381,7 +398,7 @@ __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArg
 // order for the d_rel kernel, which also adds the relative-position part of dQ.
 // REL_LDS: the compact relative-position table is staged in LDS; otherwise (large tables) its rows
 // are read from memory when a tile forms its bias table.
-template <bool REL_LDS>
+template <bool REL_LDS, bool DROP>
 __global__ void __launch_bounds__(kTileThreads, 2) bwd_q_tile_kernel(const TileArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     bf16_t* rel_s = reinterpret_cast<bf16_t*>(smem);
@@ -395,6 +412,10 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_q_tile_kernel(const TileA
     bf16_t* k_s = reinterpret_cast<bf16_t*>(smem + rel_bytes + (size_t)kTileWaves * 16 * a.bias_stride * sizeof(float)) +
                   (size_t)wave * 64 * kRowStride;                      // [32 columns][kRowStride]: K rows
     bf16_t* v_s = k_s + 32 * kRowStride;                                // the same for V rows
+    int32_t* relid_s = reinterpret_cast<int32_t*>(smem + rel_bytes + (size_t)kTileWaves * 16 * a.bias_stride * sizeof(float) +
+                                                  (size_t)kTileWaves * 64 * kRowStride * sizeof(bf16_t));   // [cid_pad], DROP
+    if (DROP)
+        for (int i = threadIdx.x; i < a.cid_pad; i += blockDim.x) relid_s[i] = i < a.num_cids ? a.cid_to_id[i] : 0;
     if (REL_LDS) {
         for (int i = threadIdx.x; i < a.cid_pad * 8; i += blockDim.x) {
             const int cid = i >> 3, c8 = (i & 7) * 8;
@@ -502,9 +523,11 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_q_tile_kernel(const TileA
     float lse2 = 0.f, dl_part = 0.f;
     float2* wp_t = a.wp;   // this (batch, head)'s pairs, in tile order: [chunk][token][16 columns]
     f32x4_t ow[4], op[4];
+    uint32_t rowh = 0;   // DROP: hash of (seed, batch*head, token j of the tile)
 
     while (cc.valid) {
         if (cc.pair == 0) {   // a new tile: its operands arrived with the rows of this pair
+            if (DROP) rowh = drop_row_hash(drop_bh_hash(a.drop_seed, cc.bh), cc.tile * 16 + j);
             qb0 = qn0; qb1 = qn1; gb0 = gn0; gb1 = gn1;
             lse2 = lse_n * kLog2e;
             wp_t = a.wp + (int64_t)cc.bh * a.num_chunks * 256;
@@ -586,7 +609,9 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_q_tile_kernel(const TileA
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const float p = cid[c][r] >= 0 ? fast_exp2((s4[c][r] + bv[c][r]) * qscale - lse2) : 0.f;
-                const float wgt = p * d4[c][r];
+                // with dropout out = sum keep p v, so dP carries the mask
+                const float keep = DROP ? drop_scale(rowh, (uint32_t)relid_s[max(cid[c][r], 0)], a.drop_thr, a.drop_inv_keep) : 1.f;
+                const float wgt = p * d4[c][r] * keep;
                 dl_part += wgt;
                 pw[c][r] = wgt;
                 pp[c][r] = p;

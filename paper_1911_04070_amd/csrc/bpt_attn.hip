@@ -151,7 +151,8 @@ TilePlan plan_tiles(const bpt_graph* g, const DeviceLimits& lim) {
     t.bias_stride = t.cid_pad + ((4 - t.cid_pad % 32) + 32) % 32;  // = 4 mod 32: the 16 token rows hit different banks
     const size_t rel = (size_t)t.cid_pad * kRelStride * sizeof(bf16_t);
     const size_t rest = (size_t)kTileWaves * 16 * t.bias_stride * sizeof(float) +
-                        (size_t)kTileWaves * 64 * kRowStride * sizeof(bf16_t);
+                        (size_t)kTileWaves * 64 * kRowStride * sizeof(bf16_t) +
+                        (size_t)t.cid_pad * sizeof(int32_t);   // relative-position ids of the compact ids (dropout)
     t.rel_lds = rel + rest <= lim.lds;
     t.lds = t.rel_lds ? rel + rest : rest;
     t.ok = t.lds <= lim.lds;
@@ -176,8 +177,11 @@ int run_bwd_q_tiles(const bpt_graph* g, const AttnArgs& a, const DeviceLimits& l
     const TilePlan tp = plan_tiles(g, lim);
     TileArgs t = {};
     fill_tile_args(t, g, a, tp);
-    return tp.rel_lds ? launch_tiles("bwd_q_tile_kernel", bwd_q_tile_kernel<true>, t, lim, tp.lds, st)
-                      : launch_tiles("bwd_q_tile_kernel", bwd_q_tile_kernel<false>, t, lim, tp.lds, st);
+    if (a.drop_thr)
+        return tp.rel_lds ? launch_tiles("bwd_q_tile_kernel", bwd_q_tile_kernel<true, true>, t, lim, tp.lds, st)
+                          : launch_tiles("bwd_q_tile_kernel", bwd_q_tile_kernel<false, true>, t, lim, tp.lds, st);
+    return tp.rel_lds ? launch_tiles("bwd_q_tile_kernel", bwd_q_tile_kernel<true, false>, t, lim, tp.lds, st)
+                      : launch_tiles("bwd_q_tile_kernel", bwd_q_tile_kernel<false, false>, t, lim, tp.lds, st);
 }
 
 void fill_tile_args(TileArgs& t, const bpt_graph* g, const AttnArgs& a, const TilePlan& tp) {
@@ -217,6 +221,9 @@ void fill_tile_args(TileArgs& t, const bpt_graph* g, const AttnArgs& a, const Ti
     t.W = g->rel_width;
     t.ctx_levels = g->ctx_levels;
     t.causal = g->causal;
+    t.drop_thr = a.drop_thr;
+    t.drop_seed = a.drop_seed;
+    t.drop_inv_keep = a.drop_inv_keep;
 }
 
 // Span rows on blocks of 32 tokens (fwd_span_tile_kernel, bwd_q_span_tile_kernel): needs the token
@@ -255,6 +262,9 @@ void fill_span_args(SpanArgs& t, const bpt_graph* g, const AttnArgs& a) {
     t.zero = g->k + 1;
     t.scale = a.scale;
     t.seq_len = a.seq_len;
+    t.drop_thr = a.drop_thr;
+    t.drop_seed = a.drop_seed;
+    t.drop_inv_keep = a.drop_inv_keep;
 }
 // forward == true: out and lse of all span rows; else delta, lse and dQ of all span rows
 int run_span_tiles(const bpt_graph* g, const AttnArgs& a, bool forward, hipStream_t st) {
@@ -263,10 +273,14 @@ int run_span_tiles(const bpt_graph* g, const AttnArgs& a, bool forward, hipStrea
     const int64_t items = (int64_t)a.BH * (g->n / kSpanTok);
     const unsigned grid = (unsigned)((items + kTileWaves - 1) / kTileWaves);
     const size_t lds = (size_t)kTileWaves * kSpanTok * kVStride * sizeof(bf16_t);
-    if (forward)
-        BPT_LAUNCH("fwd_span_tile_kernel", fwd_span_tile_kernel, dim3(grid), dim3(kTileThreads), lds, st, t);
+    if (forward && t.drop_thr)
+        BPT_LAUNCH("fwd_span_tile_kernel", fwd_span_tile_kernel<true>, dim3(grid), dim3(kTileThreads), lds, st, t);
+    else if (forward)
+        BPT_LAUNCH("fwd_span_tile_kernel", fwd_span_tile_kernel<false>, dim3(grid), dim3(kTileThreads), lds, st, t);
+    else if (t.drop_thr)
+        BPT_LAUNCH("bwd_q_span_tile_kernel", bwd_q_span_tile_kernel<true>, dim3(grid), dim3(kTileThreads), lds, st, t);
     else
-        BPT_LAUNCH("bwd_q_span_tile_kernel", bwd_q_span_tile_kernel, dim3(grid), dim3(kTileThreads), lds, st, t);
+        BPT_LAUNCH("bwd_q_span_tile_kernel", bwd_q_span_tile_kernel<false>, dim3(grid), dim3(kTileThreads), lds, st, t);
     BPT_HIP(hipGetLastError());
     if (t.L > kSpanInLevels) {
         // rows of levels 6..9 (at most 16 partials each), then the longer rows
@@ -292,8 +306,11 @@ int run_span_tiles(const bpt_graph* g, const AttnArgs& a, bool forward, hipStrea
 int run_fwd_tiles(const bpt_graph* g, AttnArgs& a, const DeviceLimits& lim, const TilePlan& tp, hipStream_t st) {
     TileArgs t = {};
     fill_tile_args(t, g, a, tp);
-    return tp.rel_lds ? launch_tiles("fwd_tile_kernel", fwd_tile_kernel<true>, t, lim, tp.lds, st)
-                      : launch_tiles("fwd_tile_kernel", fwd_tile_kernel<false>, t, lim, tp.lds, st);
+    if (a.drop_thr)
+        return tp.rel_lds ? launch_tiles("fwd_tile_kernel", fwd_tile_kernel<true, true>, t, lim, tp.lds, st)
+                          : launch_tiles("fwd_tile_kernel", fwd_tile_kernel<false, true>, t, lim, tp.lds, st);
+    return tp.rel_lds ? launch_tiles("fwd_tile_kernel", fwd_tile_kernel<true, false>, t, lim, tp.lds, st)
+                      : launch_tiles("fwd_tile_kernel", fwd_tile_kernel<false, false>, t, lim, tp.lds, st);
 }
 
 template <typename T>
@@ -303,7 +320,7 @@ int run_fwd(const bpt_graph* g, AttnArgs& a, hipStream_t st) {
     if (rc) return rc;
     if (sizeof(T) == 2) {
         const TilePlan tp = plan_tiles(g, lim);
-        if (tp.ok && a.drop_thr == 0) {   // dropout runs on the gather kernels
+        if (tp.ok) {
             if ((rc = run_fwd_tiles(g, a, lim, tp, st))) return rc;
             if (span_tiles_ok(g)) return run_span_tiles(g, a, true, st);
             use_schedule(a, g->fwd_span);  // the gather kernel below only sees span rows
@@ -362,17 +379,16 @@ int plan_bwd(const bpt_graph* g, const bpt_shape_t* s, BwdPlan* p) {
         // dense tiles for the query side: when one workgroup of the d_rel kernel can hold all ids in use
         const int cids = (g->tiles.num_cids + 31) & ~31;
         const size_t rg_lds = ((size_t)2 * cids * kRgStride + kRgRows * kRowStride + (size_t)cids * kRelStride) * sizeof(bf16_t);
-        const bool dropout = s->dropout_p > 0.f;   // the mask is formed by the gather kernels only
-        if (!dropout && plan_tiles(g, lim).ok && cids <= kRgTileMaxIds && rg_lds + 256 <= lim.lds) {
+        if (plan_tiles(g, lim).ok && cids <= kRgTileMaxIds && rg_lds + 256 <= lim.lds) {
             p->q_tiles = true;
             p->drel_tile = true;
             p->drel_part_rows = cids;
             p->drel_lds = rg_lds;
         }
-        if (!dropout && g->ktiles.num_tasks > 0 && g->ktiles.nb_pad <= 16 * kMaxBiasChunks) {
+        if (g->ktiles.num_tasks > 0 && g->ktiles.nb_pad <= 16 * kMaxBiasChunks) {
             const int parked = std::max(0, g->ktiles.nb_pad / 16 - kRegBiasChunks);   // table operands kept in LDS
             p->kv_lds = (size_t)kTileWaves * (32 * (g->ktiles.nb_pad + 1) * sizeof(float) + 64 * kRowStride * sizeof(bf16_t) +
-                                              32 * sizeof(float2) + (size_t)parked * 64 * 32);
+                                              32 * sizeof(float2) + 32 * sizeof(uint32_t) + (size_t)parked * 64 * 32);
             p->kv_tiles = p->kv_lds <= lim.lds;
         }
         p->drel_grid_y = p->drel_tile ? 1 : (p->drel_rows + kRgIds - 1) / kRgIds;
@@ -514,15 +530,20 @@ int run_bwd_q(const bpt_graph* g, const BwdPlan& p, AttnArgs& a, hipStream_t st)
     return BPT_OK;
 }
 
-template <int NBC>
-int launch_kv_tiles(const KeyArgs& t, const BwdPlan& p, const DeviceLimits& lim, hipStream_t st) {
+template <int NBC, bool DROP>
+int launch_kv_tiles_as(const KeyArgs& t, const BwdPlan& p, const DeviceLimits& lim, hipStream_t st) {
     if (p.kv_lds > 65536)
-        BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_kv_tile_kernel<NBC>),
+        BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_kv_tile_kernel<NBC, DROP>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.kv_lds));
-    const int grid = std::max(8, lim.cus * resident_blocks(bwd_kv_tile_kernel<NBC>, kTileThreads, p.kv_lds, lim) / 8 * 8);
-    BPT_LAUNCH("bwd_kv_tile_kernel", bwd_kv_tile_kernel<NBC>, dim3(grid), dim3(kTileThreads), p.kv_lds, st, t);
+    const int grid =
+        std::max(8, lim.cus * resident_blocks(bwd_kv_tile_kernel<NBC, DROP>, kTileThreads, p.kv_lds, lim) / 8 * 8);
+    BPT_LAUNCH("bwd_kv_tile_kernel", (bwd_kv_tile_kernel<NBC, DROP>), dim3(grid), dim3(kTileThreads), p.kv_lds, st, t);
     BPT_HIP(hipGetLastError());
     return BPT_OK;
+}
+template <int NBC>
+int launch_kv_tiles(const KeyArgs& t, const BwdPlan& p, const DeviceLimits& lim, hipStream_t st) {
+    return t.drop_thr ? launch_kv_tiles_as<NBC, true>(t, p, lim, st) : launch_kv_tiles_as<NBC, false>(t, p, lim, st);
 }
 
 // bf16 key side on dense tiles of key nodes
@@ -564,6 +585,9 @@ int run_bwd_kv_tiles(const bpt_graph* g, const BwdPlan& p, const AttnArgs& a, co
     t.num_chunks = kt.num_chunks;
     t.seq_len = a.seq_len;
     t.n = g->n;
+    t.drop_thr = a.drop_thr;
+    t.drop_seed = a.drop_seed;
+    t.drop_inv_keep = a.drop_inv_keep;
     int rc = BPT_ERR_UNSUPPORTED;
     switch (kt.nb_pad / 16) {
         case 1: rc = launch_kv_tiles<1>(t, p, lim, st); break;

@@ -309,6 +309,7 @@ DROPOUT = [
     ("f32", 64, 2, False, 2, 2, 0.1, None), ("f32", 256, 3, True, 1, 2, 0.5, None),
     ("bf16", 512, 4, False, 2, 2, 0.1, None), ("bf16", 2048, 8, True, 1, 2, 0.3, None),
     ("bf16", 1024, 5, False, 2, 1, 0.2, [1000, 300]), ("bf16", 4096, 40, False, 1, 1, 0.1, None),
+    ("bf16", 2048, 16, True, 2, 1, 0.25, [2048, 777]), ("bf16", 8192, 8, True, 1, 1, 0.1, None),
 ]
 
 
@@ -334,7 +335,10 @@ def test_dropout_on_attention_weights(dtype, n, k, causal, B, H, p, lengths):
         got = host(got_t)
         assert np.isfinite(got).all(), name
         res[name] = float(np.abs(got - ref).max())
-        assert res[name] <= TOL[dtype], (name, res[name])
+        # the absolute tolerance is that of a convex combination of value rows; inverted dropout multiplies a row of
+        # `out` (rounded to the tensors' dtype) by up to 1/(1-p), and the rounding step with it
+        tol = TOL[dtype] / (1.0 - p) if name == "out" else TOL[dtype]
+        assert res[name] <= tol, (name, res[name])
     # and it is a different result from the one without dropout
     out0, _ = bpt.bpt_attn_fwd(g, Q, K, V, R, scale=w.scale, seq_len=lens_d)
     assert float((out0.float() - out_d.float()).abs().max()) > 0.05
