@@ -353,3 +353,20 @@ def test_dropout_zero_is_no_dropout_and_lengths_use_global_head_indices():
     for x, y in zip(ga[:3], gb[:3]):
         assert np.array_equal(x, y)
     assert np.abs(ga[3] - gb[3]).max() < 1e-12
+
+
+def test_dropout_is_unbiased_over_seeds():
+    # inverted dropout: the mean of `out` over many masks is the `out` without dropout (a wrong scale,
+    # or a mask that ignores the seed, fails this without reference to the hash itself)
+    g = oracle.build_graph(16, 2, False)
+    Q, K, V, Rel, _ = rand_inputs(g, 1, 2, 8, seed=21)
+    want = oracle.attn_fwd(g, Q, K, V, Rel, 0.3)[0]
+    p, seeds = 0.3, 600
+    acc = np.zeros_like(want)
+    for s in range(seeds):
+        acc += oracle.attn_fwd(g, Q, K, V, Rel, 0.3, dropout=p, seed=1000 + 7 * s)[0]
+    err = np.abs(acc / seeds - want)
+    # per element: variance <= p/(1-p) * sum_e p_e^2 v_e^2 <= p/(1-p) * max|v|^2; 5 sigma of the mean
+    bound = 5 * np.sqrt(p / (1 - p) / seeds) * np.abs(V).max()
+    assert err.max() < bound, (err.max(), bound)
+    assert err.mean() < bound / 5
