@@ -214,6 +214,14 @@ def main():
     bpt.bpt_profile_enable(False)
     kernel_ms = {name: total / calls for name, (calls, total) in prof.items()}
 
+    # what a plain device-to-device copy of 256 MiB reaches on this machine (read + write), beside the published peak
+    src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    copy_ms = timed(lambda: dst.copy_(src), 10)
+    copy_gbs = 2.0 * src.numel() / (copy_ms * 1e-3) / 1e9
+    del src, dst
+
     # algorithmic bytes per launch: every edge-instance a gather kernel handles counts one
     # key row + one value row (or one query row + one dout row): 256 B in bf16, 512 B in fp32
     bh = w.B * w.H
@@ -247,6 +255,7 @@ def main():
     roofline = {
         "bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
         "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+        "device_copy_GBs": round(copy_gbs, 1),
         "traffic": MEASURED_TRAFFIC.get(w.name, {}).get(dominant),
         "launch_ms": round(kernel_ms[dominant], 4),
         "algorithmic_bytes_per_edge_instance": gather,
@@ -281,9 +290,20 @@ def main():
                 oracle.attn_bwd(og, x["Q"], x["K"], x["V"], x["Rel"], x["dO"], w.scale)
             dt += time.perf_counter() - t0
             passes += 1
+        # the same oracle on one thread, on the first (batch, head) of the workload
+        one = {k_: np.ascontiguousarray(v[:1, :1]) for k_, v in x.items() if k_ != "Rel"}
+        len0 = int(lengths[0]) if lengths is not None else w.n
+        g1 = og if lengths is None else oracle.build_graph_len(w.n, len0, w.k, w.causal)
+        t0 = time.perf_counter()
+        oracle.attn_fwd(g1, one["Q"], one["K"], one["V"], x["Rel"], w.scale, threads=1)
+        if w.backward:
+            oracle.attn_bwd(g1, one["Q"], one["K"], one["V"], x["Rel"], one["dO"], w.scale, threads=1)
+        dt1 = time.perf_counter() - t0
         cpu = {"value": round(edge_inst * passes / dt, 1), "unit": "edges/s", "cores": used, "kind": "oracle",
                "sample": "the whole workload, %d pass(es) of forward%s in fp64, %.1f s wall" % (
-                   passes, " + backward" if w.backward else "", dt)}
+                   passes, " + backward" if w.backward else "", dt),
+               "one_thread_value": round(g1.num_edges / dt1, 1),
+               "one_thread_sample": "one (batch, head) of the workload, %.2f s" % dt1}
 
     res = {
         "metric": "BPT graph-attention fwd+bwd edges/sec" if w.backward else "BPT graph-attention fwd edges/sec",

@@ -13,7 +13,7 @@ from __future__ import annotations
 
 import numpy as np
 
-from . import attn_fwd, attn_fwd_lengths, build_graph
+from . import attn_bwd, attn_bwd_lengths, attn_fwd, attn_fwd_lengths, build_graph, level_offset, num_levels
 
 
 def layer_norm(x: np.ndarray, gain: np.ndarray, bias: np.ndarray, eps: float) -> np.ndarray:
@@ -46,3 +46,82 @@ def layer_forward(n, k, causal, heads, X, Rel, p, scale, eps=1e-5, lengths=None)
     Z = layer_norm(X + O @ f64(p["Wo"]), p["g1"], p["beta1"], eps)
     F = np.maximum(Z @ f64(p["W1"]) + f64(p["b1"]), 0.0) @ f64(p["W2"]) + f64(p["b2"])
     return layer_norm(Z + F, p["g2"], p["beta2"], eps)
+
+
+def kept_rows(n: int, lengths) -> np.ndarray:
+    """[B, 2n-1] bool: node (l, m) of entry b holds a token of its sequence, m * 2^l < lengths[b]."""
+    first = np.concatenate([np.arange(n >> l, dtype=np.int64) << l for l in range(num_levels(n))])
+    assert first.shape[0] == 2 * n - 1 and level_offset(n, 1) == n
+    return first[None, :] < np.asarray(lengths, dtype=np.int64)[:, None]
+
+
+def layer_norm_backward(s, gain, eps, dy):
+    """Gradient of y = norm(s) * gain + bias with respect to s, gain and bias (rows = all leading axes)."""
+    mean = s.mean(-1, keepdims=True)
+    r = 1.0 / np.sqrt(((s - mean) ** 2).mean(-1, keepdims=True) + eps)
+    xh = (s - mean) * r
+    dxh = dy * gain
+    ds = r * (dxh - dxh.mean(-1, keepdims=True) - xh * (dxh * xh).mean(-1, keepdims=True))
+    flat = lambda a: a.reshape(-1, a.shape[-1])
+    return ds, (flat(dy) * flat(xh)).sum(0), flat(dy).sum(0)
+
+
+def layer_backward(n, k, causal, heads, X, Rel, p, dY, scale, eps=1e-5, lengths=None):
+    """Gradient of sum(H' * dY) of `layer_forward` with respect to X, the relative-position table and every
+    parameter, by the chain rule through the steps of the forward in reverse (float64).  With `lengths`, the
+    rows of dY of nodes a sequence does not keep are taken as zero.  Returns a dict: dX [B, N, d], dRel, dWq,
+    dWk, dWv, dWo, dW1, db1, dW2, db2, dg1, dbeta1, dg2, dbeta2."""
+    X = X.astype(np.float64)
+    dY = dY.astype(np.float64)
+    B, N, d = X.shape
+    D = d // heads
+    f64 = lambda a: np.asarray(a, dtype=np.float64)
+    W = {w: f64(p[w]) for w in ("Wq", "Wk", "Wv", "Wo", "W1", "W2")}
+    if lengths is not None:
+        dY = dY * kept_rows(n, lengths)[:, :, None]
+
+    def split(t):   # [B, N, d] -> [B, heads, N, D]
+        return np.ascontiguousarray(t.reshape(B, N, heads, D).transpose(0, 2, 1, 3))
+
+    def join(t):    # back
+        return t.transpose(0, 2, 1, 3).reshape(B, N, d)
+
+    # forward, keeping what the backward needs
+    Q32, K32, V32 = (split(X @ W[w]).astype(np.float32) for w in ("Wq", "Wk", "Wv"))
+    if lengths is None:
+        g = build_graph(n, k, causal)
+        out, _, _ = attn_fwd(g, Q32, K32, V32, Rel, scale)
+    else:
+        out, _, _ = attn_fwd_lengths(n, k, causal, lengths, Q32, K32, V32, Rel, scale)
+    O = join(out)
+    S1 = X + O @ W["Wo"]
+    Z = layer_norm(S1, p["g1"], p["beta1"], eps)
+    Hpre = Z @ W["W1"] + f64(p["b1"])
+    F = np.maximum(Hpre, 0.0)
+    S2 = Z + F @ W["W2"] + f64(p["b2"])
+
+    # backward
+    res = {}
+    rows = lambda a: a.reshape(-1, a.shape[-1])
+    dS2, res["dg2"], res["dbeta2"] = layer_norm_backward(S2, f64(p["g2"]), eps, dY)
+    res["db2"] = rows(dS2).sum(0)
+    res["dW2"] = rows(F).T @ rows(dS2)
+    dH = (dS2 @ W["W2"].T) * (Hpre > 0.0)
+    res["db1"] = rows(dH).sum(0)
+    res["dW1"] = rows(Z).T @ rows(dH)
+    dZ = dS2 + dH @ W["W1"].T
+    dS1, res["dg1"], res["dbeta1"] = layer_norm_backward(S1, f64(p["g1"]), eps, dZ)
+    res["dWo"] = rows(O).T @ rows(dS1)
+    dO = split(dS1 @ W["Wo"].T).astype(np.float32)   # the attention oracle takes float inputs
+    if lengths is None:
+        dQ, dK, dV, dRel, _ = attn_bwd(g, Q32, K32, V32, Rel, dO, scale)
+    else:
+        dQ, dK, dV, dRel = attn_bwd_lengths(n, k, causal, lengths, Q32, K32, V32, Rel, dO, scale)[:4]
+    res["dRel"] = dRel
+    dX = dS1.copy()
+    for name, grad in (("Wq", dQ), ("Wk", dK), ("Wv", dV)):
+        gj = join(grad)
+        res["d" + name] = rows(X).T @ rows(gj)
+        dX += gj @ W[name].T
+    res["dX"] = dX
+    return res

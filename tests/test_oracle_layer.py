@@ -84,3 +84,135 @@ def test_k_at_least_n_is_a_transformer_encoder_layer_over_the_tokens():
         enc.norm2.bias.copy_(t(p["beta2"]))
         ref = enc(t(X[:, :n])).numpy()
     assert np.abs(Y[:, :n] - ref).max() < 1e-6
+
+
+# ------------------------------------------------------------------ backward of the layer
+from oracle.layer import kept_rows, layer_backward, layer_norm_backward   # noqa: E402
+
+PARAMS = ("Wq", "Wk", "Wv", "Wo", "W1", "b1", "W2", "b2", "g1", "beta1", "g2", "beta2")
+
+
+def test_layer_norm_backward_is_autograd_of_the_library_routine():
+    rng = np.random.default_rng(1)
+    s, dy = rng.standard_normal((4, 5, 128)), rng.standard_normal((4, 5, 128))
+    g, b = 1 + 0.3 * rng.standard_normal(128), rng.standard_normal(128)
+    st, gt, bt = (torch.tensor(a, requires_grad=True) for a in (s, g, b))
+    torch.nn.functional.layer_norm(st, (128,), gt, bt, 1e-5).backward(torch.tensor(dy))
+    ds, dg, db = layer_norm_backward(s, g, 1e-5, dy)
+    assert np.abs(ds - st.grad.numpy()).max() < 1e-12
+    assert np.abs(dg - gt.grad.numpy()).max() < 1e-12
+    assert np.abs(db - bt.grad.numpy()).max() < 1e-12
+
+
+def dense_graph_tables(graphs, N):
+    """Per batch entry: [N, N] edge mask and relative-position ids, from the (pinned) graph builder."""
+    masks, ids = [], []
+    for g in graphs:
+        m, i = np.zeros((N, N), dtype=bool), np.zeros((N, N), dtype=np.int64)
+        for u in range(N):
+            b, e = g.row_ptr[u], g.row_ptr[u + 1]
+            m[u, g.col[b:e]] = True
+            i[u, g.col[b:e]] = g.rel[b:e]
+        masks.append(m)
+        ids.append(i)
+    return np.stack(masks), np.stack(ids)
+
+
+def torch_layer(X, Rel, P, masks, ids, heads, scale, eps=1e-5):
+    """The layer as a composition of torch routines, attention as a dense masked softmax over all nodes."""
+    B, N, d = X.shape
+    lin, ln = torch.nn.functional.linear, torch.nn.functional.layer_norm
+    Q, K, V = (lin(X, P[w].T).reshape(B, N, heads, 64).permute(0, 2, 1, 3) for w in ("Wq", "Wk", "Wv"))
+    R = Rel.reshape(-1, 64)[torch.tensor(ids)]                                   # [B, N, N, 64]
+    S = scale * (torch.einsum("bhud,bhvd->bhuv", Q, K) + torch.einsum("bhud,buvd->bhuv", Q, R))
+    S = S.masked_fill(~torch.tensor(masks)[:, None], float("-inf"))
+    Pm = torch.softmax(S, -1)
+    Pm = torch.where(torch.tensor(masks)[:, None], Pm, torch.zeros_like(Pm))   # rows without edges: zeros, not nan
+    O = (Pm @ V).permute(0, 2, 1, 3).reshape(B, N, d)
+    Z = ln(X + lin(O, P["Wo"].T), (d,), P["g1"], P["beta1"], eps)
+    F = lin(torch.relu(lin(Z, P["W1"].T, P["b1"])), P["W2"].T, P["b2"])
+    return ln(Z + F, (d,), P["g2"], P["beta2"], eps)
+
+
+def check_against_autograd(n, k, causal, lengths, seed):
+    heads, d_ff, B = 2, 192, 2
+    d = heads * 64
+    rng = np.random.default_rng(seed)
+    g = oracle.build_graph(n, k, causal)
+    N = g.num_nodes
+    X = rng.standard_normal((B, N, d)).astype(np.float32)
+    dY = rng.standard_normal((B, N, d)).astype(np.float32)
+    Rel = (0.3 * rng.standard_normal((g.num_levels, g.rel_width, 64))).astype(np.float32)
+    p = make_params(rng, d, d_ff)
+    got = layer_backward(n, k, causal, heads, X, Rel, p, dY, 0.125, lengths=lengths)
+    graphs = [g] * B if lengths is None else [oracle.build_graph_len(n, L, k, causal) for L in lengths]
+    masks, ids = dense_graph_tables(graphs, N)
+    t = lambda a: torch.tensor(np.asarray(a, dtype=np.float64), requires_grad=True)
+    Xt, Rt, P = t(X), t(Rel), {w: t(p[w]) for w in PARAMS}
+    Y = torch_layer(Xt, Rt, P, masks, ids, heads, 0.125)
+    dYt = torch.tensor(dY.astype(np.float64))
+    if lengths is not None:
+        dYt = dYt * torch.tensor(kept_rows(n, lengths))[:, :, None]
+    Y.backward(dYt)
+    ref = {"dX": Xt.grad, "dRel": Rt.grad}
+    ref.update({"d" + w: P[w].grad for w in PARAMS})
+    assert sorted(got) == sorted(ref)
+    for name, r in ref.items():
+        r = r.numpy()
+        # the attention oracle rounds its inputs to float32: 1e-7 relative
+        assert np.abs(got[name] - r).max() <= 2e-5 * max(1.0, np.abs(r).max()), name
+    return got
+
+
+def test_layer_backward_equals_autograd_through_a_dense_composition():
+    check_against_autograd(16, 2, False, None, 3)
+    check_against_autograd(32, 3, True, None, 4)
+
+
+def test_layer_backward_with_lengths():
+    got = check_against_autograd(32, 2, False, [32, 11], 5)
+    gone = ~kept_rows(32, [32, 11])
+    assert gone[1].sum() > 0 and np.abs(got["dX"][gone]).max() == 0      # rows a sequence does not keep get no gradient
+
+
+def test_layer_backward_for_k_at_least_n_is_the_transformer_encoder_layer():
+    # Sec. 3.3 again: with gradients arriving at the token rows only, the token rows and all parameters
+    # get the gradients of torch's post-norm encoder layer
+    n, heads, d_ff = 16, 2, 128
+    d = heads * 64
+    rng = np.random.default_rng(10)
+    g = oracle.build_graph(n, n, False)
+    X = rng.standard_normal((1, g.num_nodes, d)).astype(np.float32)
+    dY = rng.standard_normal((1, g.num_nodes, d)).astype(np.float32)
+    dY[:, n:] = 0
+    Rel = np.zeros((g.num_levels, g.rel_width, 64), dtype=np.float32)
+    p = make_params(rng, d, d_ff)
+    got = layer_backward(n, n, False, heads, X, Rel, p, dY, 0.125)
+    enc = torch.nn.TransformerEncoderLayer(d, heads, d_ff, dropout=0.0, activation="relu", batch_first=True,
+                                           norm_first=False, dtype=torch.float64)
+    t = lambda a: torch.tensor(np.asarray(a, dtype=np.float64))
+    with torch.no_grad():
+        enc.self_attn.in_proj_weight.copy_(torch.cat([t(p["Wq"]).T, t(p["Wk"]).T, t(p["Wv"]).T]))
+        enc.self_attn.in_proj_bias.zero_()
+        enc.self_attn.out_proj.weight.copy_(t(p["Wo"]).T)
+        enc.self_attn.out_proj.bias.zero_()
+        enc.linear1.weight.copy_(t(p["W1"]).T)
+        enc.linear1.bias.copy_(t(p["b1"]))
+        enc.linear2.weight.copy_(t(p["W2"]).T)
+        enc.linear2.bias.copy_(t(p["b2"]))
+        enc.norm1.weight.copy_(t(p["g1"]))
+        enc.norm1.bias.copy_(t(p["beta1"]))
+        enc.norm2.weight.copy_(t(p["g2"]))
+        enc.norm2.bias.copy_(t(p["beta2"]))
+    Xt = t(X[:, :n]).requires_grad_(True)
+    enc(Xt).backward(t(dY[:, :n]))
+    tol = lambda r: 2e-5 * max(1.0, float(np.abs(r).max()))
+    close = lambda a, r: np.abs(a - r).max() <= tol(r)
+    assert close(got["dX"][:, :n], Xt.grad.numpy())
+    wq, wk, wv = (w.numpy().T for w in enc.self_attn.in_proj_weight.grad.split(d))
+    assert close(got["dWq"], wq) and close(got["dWk"], wk) and close(got["dWv"], wv)
+    assert close(got["dWo"], enc.self_attn.out_proj.weight.grad.numpy().T)
+    assert close(got["dW1"], enc.linear1.weight.grad.numpy().T) and close(got["db1"], enc.linear1.bias.grad.numpy())
+    assert close(got["dW2"], enc.linear2.weight.grad.numpy().T) and close(got["db2"], enc.linear2.bias.grad.numpy())
+    assert close(got["dg1"], enc.norm1.weight.grad.numpy()) and close(got["dbeta1"], enc.norm1.bias.grad.numpy())
+    assert close(got["dg2"], enc.norm2.weight.grad.numpy()) and close(got["dbeta2"], enc.norm2.bias.grad.numpy())
