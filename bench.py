@@ -59,7 +59,8 @@ def parse():
 
 
 def bench_layer(args, w, bpt, torch, np):
-    """Forward of one graph layer (Sec. 3.3) on the workload's shape: d = heads * 64, d_ff = 4 d, random bf16 weights."""
+    """Forward + backward of one graph layer (Sec. 3.3) on the workload's shape: d = heads * 64, d_ff = 4 d, random
+    bf16 weights."""
     from paper_1911_04070_amd.workloads import make_lengths
     d, d_ff = w.H * w.D, 4 * w.H * w.D
     g = bpt.bpt_build_graph(w.n, w.k, w.causal)
@@ -75,29 +76,45 @@ def bench_layer(args, w, bpt, torch, np):
              beta2=rnd(d, s=0.1))
     lens_d = torch.from_numpy(make_lengths(w)).cuda() if w.length_mix else None
     Y = torch.empty_like(X)
-    ws = torch.empty(int(bpt.load_library().bpt_layer_fwd_workspace(g.handle, w.B, w.H, d_ff)) + 256, dtype=torch.uint8,
-                     device="cuda")
-    step = lambda: bpt.bpt_layer_fwd(g, X, R, p, w.H, scale=w.scale, seq_len=lens_d, out=Y, workspace=ws)
+    dY = rnd(w.B, g.num_nodes, d).to(torch.bfloat16)
+    dX = torch.empty_like(X)
+    d_rel = torch.empty(R.shape, dtype=torch.float32, device="cuda")
+    grads = {"d" + k_: torch.empty(v.shape, dtype=torch.float32, device="cuda") for k_, v in p.items()}
+    fws, bws = bpt.layer_workspace_bytes(g, w.B, w.H, d_ff)
+    ws = torch.empty(fws + 256, dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(bws + 256, dtype=torch.uint8, device="cuda")
+    fwd = lambda: bpt.bpt_layer_fwd(g, X, R, p, w.H, scale=w.scale, seq_len=lens_d, out=Y, workspace=ws)
+    bwd = lambda: bpt.bpt_layer_bwd(g, X, R, p, w.H, ws, dY, scale=w.scale, seq_len=lens_d, dX=dX, grads=grads, d_rel=d_rel,
+                                    workspace=ws_b)
+
+    def step():
+        fwd()
+        bwd()
+
+    def wall_ms(fn):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / args.steps
+
     for _ in range(args.warmup + 2):                         # the first GEMM calls load the library's kernels
         step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms = wall_ms(step)
+    ms_fwd = wall_ms(fwd)
     bpt.bpt_profile_enable(True)
     for _ in range(5):
         step()
     torch.cuda.synchronize()
-    own = {name: total / calls for name, (calls, total) in bpt.bpt_profile_report().items()}
+    own = {name: total / 5 for name, (calls, total) in bpt.bpt_profile_report().items()}   # ms per step, all its launches
     bpt.bpt_profile_enable(False)
     rows = w.B * g.num_nodes
-    flops = 2.0 * rows * (4 * d * d + 2 * d * d_ff)
+    flops = 3 * 2.0 * rows * (4 * d * d + 2 * d * d_ff)       # the backward has two products per forward product
     print(json.dumps({
-        "metric": "BPT graph layer forward node rows/sec", "value": round(rows / (ms * 1e-3), 1), "unit": "rows/s",
+        "metric": "BPT graph layer fwd+bwd node rows/sec", "value": round(rows / (ms * 1e-3), 1), "unit": "rows/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
-        "dtype": "bf16", "data": "synthetic", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic", "vs_baseline": None, "forward_ms": round(ms_fwd, 4),
         "config": {"workload": w.name + "+layer", "n": w.n, "k": w.k, "causal": w.causal, "batch": w.B, "heads": w.H,
                    "d_model": d, "d_ff": d_ff, "node_rows": rows},
         "dense_TFLOPs": round(flops / (ms * 1e-3) / 1e12, 1),

@@ -195,20 +195,50 @@ typedef struct {
 } bpt_layer_params_t;
 
 /* Sec. 3.1 (Transformer layer) and Sec. 3.3 (the update of the graph, one iteration of its
- * loop), forward only, bf16:  Z = norm(X + GSA(G, X)),  Y = norm(Z + FFN(Z)),  with
+ * loop), forward, bf16:  Z = norm(X + GSA(G, X)),  Y = norm(Z + FFN(Z)),  with
  * GSA(G, X) = [head_1 .. head_H] Wo, the heads being eq. (8) on Q = X Wq, K = X Wk, V = X Wv,
  * FFN(z) = max(0, z W1 + b1) W2 + b2, norm = layer normalisation over the d features (biased
  * variance).  X and Y are [B][N][d] bf16, contiguous, N = 2n-1 rows per batch entry in node-id
  * order (span rows of the first layer are zero, Sec. 3.3); all nodes are updated from the same
  * X.  rel, scale and seq_len as for bpt_attn_fwd (with seq_len, rows of nodes that are not
  * kept hold unspecified values).  The dense maps run as rocBLAS GEMMs with fp32 accumulation;
- * Q, K, V, the attention output, Z and the hidden FFN activations are stored in bf16.
+ * Q, K, V, the attention output, Z and the hidden FFN activations are stored in bf16 and stay
+ * in the workspace for bpt_layer_bwd.
  * workspace: device memory of at least bpt_layer_fwd_workspace bytes; nothing is allocated
  * except, once per device, the rocBLAS handle.  H * 64 <= 2048. */
 size_t bpt_layer_fwd_workspace(const bpt_graph_t* g, int32_t B, int32_t H, int32_t d_ff);
 int bpt_layer_fwd(const bpt_graph_t* g, int32_t B, int32_t H, float scale, const int32_t* seq_len, const void* rel,
                   const void* X, const bpt_layer_params_t* p, void* Y, void* workspace, size_t workspace_bytes,
                   void* stream);
+
+/* Gradients of the parameters of one layer, device arrays in fp32 with the shapes of the
+ * parameters they belong to; every array is overwritten, none may be NULL. */
+typedef struct {
+    float *dWq, *dWk, *dWv, *dWo;  /* [d][d] */
+    float *dW1, *db1;              /* [d][d_ff], [d_ff] */
+    float *dW2, *db2;              /* [d_ff][d], [d] */
+    float *dg1, *dbeta1;           /* [d] */
+    float *dg2, *dbeta2;           /* [d] */
+} bpt_layer_grads_t;
+
+/* Backward of bpt_layer_fwd (the chain rule through the steps of Sec. 3.1 / Sec. 3.3 listed
+ * there, in reverse): given dY = the gradient of a scalar with respect to Y, [B][N][d] bf16,
+ * writes dX [B][N][d] bf16, d_rel [levels][rel_width][64] fp32 (as bpt_attn_bwd) and the
+ * gradients of all parameters.  g, B, H, scale, seq_len, rel, X and p must be those of the
+ * forward call, and fwd_workspace its workspace, unchanged since that call returned: it
+ * holds the activations the backward reads (Q, K, V, the attention output and lse, the two
+ * pre-normalisation sums with their means and reciprocal deviations, Z, the hidden FFN
+ * activations).  With seq_len, rows of dY of nodes that are not kept are taken as zero and
+ * the same rows of dX are zero.  The dense maps run as rocBLAS GEMMs (bf16 operands: the
+ * fp32 gradients of the attention are rounded to bf16 before their projections; fp32
+ * accumulation); sums over rows (biases, gains) are formed in a fixed order, so results are
+ * run-to-run identical as far as the GEMM library's are.  workspace: at least
+ * bpt_layer_bwd_workspace bytes of device memory; nothing is allocated.  d_ff <= 8192. */
+size_t bpt_layer_bwd_workspace(const bpt_graph_t* g, int32_t B, int32_t H, int32_t d_ff);
+int bpt_layer_bwd(const bpt_graph_t* g, int32_t B, int32_t H, float scale, const int32_t* seq_len, const void* rel,
+                  const void* X, const bpt_layer_params_t* p, const void* fwd_workspace, size_t fwd_workspace_bytes,
+                  const void* dY, void* dX, float* d_rel, const bpt_layer_grads_t* grads, void* workspace,
+                  size_t workspace_bytes, void* stream);
 
 /* Sec. 3.2 with the rule for shorter sequences stated at the top of this header: the number
  * of edges of the graph over n tokens with density k that a sequence of len tokens keeps

@@ -23,7 +23,8 @@ EXPORTS = [
     "bpt_build_graph", "bpt_graph_info", "bpt_graph_csr", "bpt_graph_transposed", "bpt_graph_to_host",
     "bpt_graph_transposed_to_host", "bpt_graph_destroy", "bpt_attn_fwd_workspace", "bpt_attn_bwd_workspace",
     "bpt_attn_fwd", "bpt_attn_bwd", "bpt_attn_bwd_query_side", "bpt_attn_bwd_key_side", "bpt_profile_enable",
-    "bpt_profile_report", "bpt_layer_fwd_workspace", "bpt_layer_fwd", "bpt_count_edges", "bpt_strerror",
+    "bpt_profile_report", "bpt_layer_fwd_workspace", "bpt_layer_fwd", "bpt_layer_bwd_workspace", "bpt_layer_bwd",
+    "bpt_count_edges", "bpt_strerror",
 ]
 
 
@@ -37,6 +38,13 @@ class BptShape(ctypes.Structure):
 class BptLayerParams(ctypes.Structure):
     _fields_ = [(name, ctypes.c_void_p) for name in ("Wq", "Wk", "Wv", "Wo", "W1", "W2", "b1", "b2", "g1", "beta1", "g2",
                                                      "beta2")] + [("d_ff", ctypes.c_int32), ("eps", ctypes.c_float)]
+
+
+GRAD_NAMES = ("dWq", "dWk", "dWv", "dWo", "dW1", "db1", "dW2", "db2", "dg1", "dbeta1", "dg2", "dbeta2")
+
+
+class BptLayerGrads(ctypes.Structure):
+    _fields_ = [(name, ctypes.c_void_p) for name in GRAD_NAMES]
 
 
 class BptError(RuntimeError):
@@ -94,6 +102,11 @@ def load_library() -> ctypes.CDLL:
     L.bpt_layer_fwd_workspace.argtypes = [vp, i32, i32, i32]
     L.bpt_layer_fwd.restype = ctypes.c_int
     L.bpt_layer_fwd.argtypes = [vp, i32, i32, ctypes.c_float, vp, vp, vp, P(BptLayerParams), vp, vp, sz, vp]
+    L.bpt_layer_bwd_workspace.restype = sz
+    L.bpt_layer_bwd_workspace.argtypes = [vp, i32, i32, i32]
+    L.bpt_layer_bwd.restype = ctypes.c_int
+    L.bpt_layer_bwd.argtypes = [vp, i32, i32, ctypes.c_float, vp, vp, vp, P(BptLayerParams), vp, sz, vp, vp, vp,
+                                P(BptLayerGrads), vp, sz, vp]
     L.bpt_count_edges.restype = ctypes.c_int
     L.bpt_count_edges.argtypes = [i32, i32, i32, i32, P(i64)]
     L.bpt_strerror.restype = ctypes.c_char_p
@@ -310,12 +323,9 @@ def bpt_attn_bwd_key_side(g: Graph, Q, K, V, rel, lse, dout, dK, dV, workspace, 
     return dK, dV
 
 
-def bpt_layer_fwd(g: Graph, X: torch.Tensor, rel: torch.Tensor, params: dict, heads: int, scale: Optional[float] = None,
-                  eps: float = 1e-5, seq_len: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
-                  workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """One graph layer, forward (Sec. 3.3): X [B, N, heads*64] bf16 -> Y of the same shape.  params: Wq, Wk, Wv,
-    Wo [d, d], W1 [d, d_ff], W2 [d_ff, d] in bf16 and b1, b2, g1, beta1, g2, beta2 in fp32, all contiguous cuda tensors."""
-    L = load_library()
+def _layer_args(g: Graph, X: torch.Tensor, rel: torch.Tensor, params: dict, heads: int, eps: float,
+                seq_len: Optional[torch.Tensor]):
+    """Checks the tensors of a layer call; returns (d_ff, the parameter struct, the seq_len pointer)."""
     d = heads * 64
     if X.dtype != torch.bfloat16 or X.dim() != 3 or X.shape[1] != g.num_nodes or X.shape[2] != d or not X.is_contiguous():
         raise ValueError("X must be a contiguous bf16 [B, %d, %d] tensor" % (g.num_nodes, d))
@@ -336,6 +346,17 @@ def bpt_layer_fwd(g: Graph, X: torch.Tensor, rel: torch.Tensor, params: dict, he
         lens = seq_len.data_ptr()
     lp = BptLayerParams(*[params[n].data_ptr() for n in ("Wq", "Wk", "Wv", "Wo", "W1", "W2", "b1", "b2", "g1", "beta1",
                                                           "g2", "beta2")], d_ff, float(eps))
+    return d_ff, lp, lens
+
+
+def bpt_layer_fwd(g: Graph, X: torch.Tensor, rel: torch.Tensor, params: dict, heads: int, scale: Optional[float] = None,
+                  eps: float = 1e-5, seq_len: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
+                  workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """One graph layer, forward (Sec. 3.3): X [B, N, heads*64] bf16 -> Y of the same shape.  params: Wq, Wk, Wv,
+    Wo [d, d], W1 [d, d_ff], W2 [d_ff, d] in bf16 and b1, b2, g1, beta1, g2, beta2 in fp32, all contiguous cuda tensors.
+    Pass a `workspace` (layer_workspace_bytes) to keep the activations for bpt_layer_bwd."""
+    L = load_library()
+    d_ff, lp, lens = _layer_args(g, X, rel, params, heads, eps, seq_len)
     if out is None:
         out = torch.empty_like(X)
     need = int(L.bpt_layer_fwd_workspace(g.handle, X.shape[0], heads, d_ff))
@@ -345,6 +366,46 @@ def bpt_layer_fwd(g: Graph, X: torch.Tensor, rel: torch.Tensor, params: dict, he
                            ctypes.byref(lp), out.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream_ptr()),
            "bpt_layer_fwd")
     return out
+
+
+def layer_workspace_bytes(g: Graph, B: int, heads: int, d_ff: int) -> Tuple[int, int]:
+    """Bytes of workspace bpt_layer_fwd and bpt_layer_bwd need."""
+    L = load_library()
+    return (int(L.bpt_layer_fwd_workspace(g.handle, B, heads, d_ff)), int(L.bpt_layer_bwd_workspace(g.handle, B, heads, d_ff)))
+
+
+def bpt_layer_bwd(g: Graph, X: torch.Tensor, rel: torch.Tensor, params: dict, heads: int, fwd_workspace: torch.Tensor,
+                  dY: torch.Tensor, scale: Optional[float] = None, eps: float = 1e-5,
+                  seq_len: Optional[torch.Tensor] = None, dX: Optional[torch.Tensor] = None,
+                  grads: Optional[dict] = None, d_rel: Optional[torch.Tensor] = None,
+                  workspace: Optional[torch.Tensor] = None):
+    """Backward of bpt_layer_fwd, called with the same arguments and the workspace that call filled.  dY: bf16
+    like X.  Returns (dX bf16, d_rel fp32, grads: dict of fp32 tensors named dWq ... dbeta2, shaped like their
+    parameters)."""
+    L = load_library()
+    d_ff, lp, lens = _layer_args(g, X, rel, params, heads, eps, seq_len)
+    if dY.dtype != torch.bfloat16 or dY.shape != X.shape or not dY.is_contiguous() or dY.device != X.device:
+        raise ValueError("dY must be a contiguous bf16 tensor shaped like X")
+    if dX is None:
+        dX = torch.empty_like(X)
+    if d_rel is None:
+        d_rel = torch.empty(rel.shape, dtype=torch.float32, device=X.device)
+    if grads is None:
+        grads = {"d" + n: torch.empty(params[n].shape, dtype=torch.float32, device=X.device)
+                 for n in ("Wq", "Wk", "Wv", "Wo", "W1", "b1", "W2", "b2", "g1", "beta1", "g2", "beta2")}
+    for name in GRAD_NAMES:
+        t = grads[name]
+        if t.dtype != torch.float32 or t.shape != params[name[1:]].shape or not t.is_contiguous() or t.device != X.device:
+            raise ValueError("gradient %s must be a contiguous fp32 tensor shaped like its parameter" % name)
+    lg = BptLayerGrads(*[grads[n].data_ptr() for n in GRAD_NAMES])
+    need = int(L.bpt_layer_bwd_workspace(g.handle, X.shape[0], heads, d_ff))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=X.device)
+    _check(L.bpt_layer_bwd(g.handle, X.shape[0], heads, float(scale) if scale else 0.0, lens, rel.data_ptr(), X.data_ptr(),
+                           ctypes.byref(lp), fwd_workspace.data_ptr(), fwd_workspace.numel(), dY.data_ptr(), dX.data_ptr(),
+                           d_rel.data_ptr(), ctypes.byref(lg), workspace.data_ptr(), workspace.numel(), _stream_ptr()),
+           "bpt_layer_bwd")
+    return dX, d_rel, grads
 
 
 class GraphAttentionFunction(torch.autograd.Function):

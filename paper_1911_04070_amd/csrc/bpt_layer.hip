@@ -1,12 +1,14 @@
-// The graph layer around graph self-attention, forward (Sec. 3.1 and Sec. 3.3, the update of the graph):
+// The graph layer around graph self-attention (Sec. 3.1 and Sec. 3.3, the update of the graph):
 //   Z = norm(X + [head_1 .. head_H] Wo),   Y = norm(Z + max(0, Z W1 + b1) W2 + b2)
-// for all 2n-1 nodes.  The dense maps are plain library GEMMs (rocBLAS, bf16 operands, fp32
-// accumulation); attention is this library's own forward on the [B][N][H][64] layout the
-// projections produce (no transposes); residual + bias + layer normalisation and bias + ReLU are
-// the two small kernels below.
+// for all 2n-1 nodes, forward and backward.  The dense maps are plain library GEMMs (rocBLAS,
+// bf16 operands, fp32 accumulation); attention is this library's own forward and backward on the
+// [B][N][H][64] layout the projections produce (no transposes); residual + bias + layer
+// normalisation, bias + ReLU, their backward counterparts and the fixed-order column sums are
+// the small kernels below.
 #include <hip/hip_runtime.h>
 #include <rocblas/rocblas.h>
 
+#include <algorithm>
 #include <mutex>
 
 #include "bpt_internal.h"
@@ -26,7 +28,7 @@ __device__ __forceinline__ uint32_t f32_to_bf16(float f) { return (uint32_t)__bu
 __global__ void __launch_bounds__(256) residual_layer_norm_kernel(const bf16_t* __restrict__ x, const float* __restrict__ a,
                                                                   const float* __restrict__ bias, const float* __restrict__ gain,
                                                                   const float* __restrict__ beta, bf16_t* __restrict__ y,
-                                                                  int64_t rows, int d, float eps) {
+                                                                  float2* __restrict__ stats, int64_t rows, int d, float eps) {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     if (row >= rows) return;
@@ -65,6 +67,7 @@ __global__ void __launch_bounds__(256) residual_layer_norm_kernel(const bf16_t* 
 #pragma unroll
     for (int s = 1; s < 64; s <<= 1) sq += __shfl_xor(sq, s);
     const float inv = rsqrtf(sq / (float)d + eps);
+    if (lane == 0) stats[row] = make_float2(mean, inv);   // what the backward normalises the row with
 #pragma unroll
     for (int i = 0; i < kLnMaxChunks; ++i) {
         const int c = lane + 64 * i;
@@ -98,6 +101,264 @@ __global__ void __launch_bounds__(256) bias_relu_kernel(bf16_t* __restrict__ f, 
     *reinterpret_cast<uint4*>(f + i * 8) = make_uint4(x[0], x[1], x[2], x[3]);
 }
 
+// first token of a node of the tree over n = 2^lg tokens (ids are level-major)
+__device__ __forceinline__ int first_token_of(int id, int lg) {
+    const int x = (2 << lg) - id;
+    const int level = lg - (31 - __clz(x - 1));
+    return (((2 << lg) >> level) - x) << level;
+}
+
+// Backward of y = norm(s) * gain + beta with s = x + a + bias (as residual_layer_norm_kernel formed it;
+// `stats` = its (mean, 1/deviation) per row):  dxh = dy * gain,
+//   ds = (dxh - mean(dxh) - xh * mean(dxh * xh)) / deviation,   xh = (s - mean) / deviation,
+// with dy = dy_b (bf16) + dy_f (fp32, may be null).  ds is written in bf16.  A wavefront walks rows
+// `wave, wave + waves, ...` and keeps the column sums of dy * xh (gain), dy (beta) and ds (the bias
+// inside s) of its rows in registers; the four wavefronts of a workgroup add theirs in a fixed order
+// and the workgroup writes one row of `partials` [gridDim.x][3][d].  With seq_len, rows of nodes the
+// sequence does not keep count as dy = 0.
+template <int CHUNKS>   // 8-element chunks per lane: d <= 512 * CHUNKS
+__global__ void __launch_bounds__(256) layer_norm_bwd_kernel(const bf16_t* __restrict__ dy_b, const float* __restrict__ dy_f,
+                                                             const bf16_t* __restrict__ x, const float* __restrict__ a,
+                                                             const float* __restrict__ bias, const float* __restrict__ gain,
+                                                             const float2* __restrict__ stats, bf16_t* __restrict__ ds,
+                                                             float* __restrict__ partials, int64_t rows, int d,
+                                                             const int32_t* __restrict__ seq_len, int N, int lg) {
+    extern __shared__ float red_s[];   // wavefronts 1..3: [wavefront - 1][sum][d columns]
+    auto red = [&](int w, int which, int col) -> float& { return red_s[(w * 3 + which) * d + col]; };
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nchunk = d >> 3;
+    float sg[CHUNKS][8], sb[CHUNKS][8], ss[CHUNKS][8];
+#pragma unroll
+    for (int i = 0; i < CHUNKS; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sg[i][e] = sb[i][e] = ss[i][e] = 0.f;
+    const int64_t stride = (int64_t)gridDim.x * 4;
+    for (int64_t row = (int64_t)blockIdx.x * 4 + wave; row < rows; row += stride) {
+        bool kept = true;
+        if (seq_len) {
+            const int b = (int)(row / N), node = (int)(row - (int64_t)b * N);
+            kept = first_token_of(node, lg) < min(max(seq_len[b], 0), 1 << lg);
+        }
+        const float2 st = stats[row];
+        float xh[CHUNKS][8], dxh[CHUNKS][8];
+        float m1 = 0.f, m2 = 0.f;
+#pragma unroll
+        for (int i = 0; i < CHUNKS; ++i) {
+            const int c = lane + 64 * i;
+            if (c < nchunk) {
+                const int64_t at = row * d + c * 8;
+                const uint4 xw = *reinterpret_cast<const uint4*>(x + at);
+                const uint4 gw = *reinterpret_cast<const uint4*>(dy_b + at);
+                const float4 a0 = *reinterpret_cast<const float4*>(a + at), a1 = *reinterpret_cast<const float4*>(a + at + 4);
+                float4 f0 = make_float4(0.f, 0.f, 0.f, 0.f), f1 = f0;
+                if (dy_f) {
+                    f0 = *reinterpret_cast<const float4*>(dy_f + at);
+                    f1 = *reinterpret_cast<const float4*>(dy_f + at + 4);
+                }
+                const uint32_t xv[4] = {xw.x, xw.y, xw.z, xw.w}, gv[4] = {gw.x, gw.y, gw.z, gw.w};
+                const float av[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+                const float fv[8] = {f0.x, f0.y, f0.z, f0.w, f1.x, f1.y, f1.z, f1.w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float xe = (e & 1) ? __uint_as_float(xv[e >> 1] & 0xFFFF0000u) : bf16_to_f32(xv[e >> 1] & 0xFFFFu);
+                    const float ge = (e & 1) ? __uint_as_float(gv[e >> 1] & 0xFFFF0000u) : bf16_to_f32(gv[e >> 1] & 0xFFFFu);
+                    const float dye = kept ? ge + fv[e] : 0.f;
+                    const float s = xe + av[e] + (bias ? bias[c * 8 + e] : 0.f);
+                    xh[i][e] = (s - st.x) * st.y;
+                    dxh[i][e] = dye * gain[c * 8 + e];
+                    m1 += dxh[i][e];
+                    m2 += dxh[i][e] * xh[i][e];
+                    sg[i][e] += dye * xh[i][e];
+                    sb[i][e] += dye;
+                }
+            }
+        }
+#pragma unroll
+        for (int s = 1; s < 64; s <<= 1) {
+            m1 += __shfl_xor(m1, s);
+            m2 += __shfl_xor(m2, s);
+        }
+        m1 /= (float)d;
+        m2 /= (float)d;
+#pragma unroll
+        for (int i = 0; i < CHUNKS; ++i) {
+            const int c = lane + 64 * i;
+            if (c < nchunk) {
+                uint32_t o[4];
+                float r[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    r[e] = st.y * (dxh[i][e] - m1 - xh[i][e] * m2);
+                    ss[i][e] += r[e];
+                }
+#pragma unroll
+                for (int e = 0; e < 8; e += 2) o[e >> 1] = f32_to_bf16(r[e]) | (f32_to_bf16(r[e + 1]) << 16);
+                *reinterpret_cast<uint4*>(ds + row * d + c * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+            }
+        }
+    }
+    // wavefronts 1..3 hand their sums to wavefront 0, which adds them in order and writes the workgroup's row
+#pragma unroll
+    for (int i = 0; i < CHUNKS; ++i) {
+        const int c = lane + 64 * i;
+        if (c < nchunk && wave > 0)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                red(wave - 1, 0, c * 8 + e) = sg[i][e];
+                red(wave - 1, 1, c * 8 + e) = sb[i][e];
+                red(wave - 1, 2, c * 8 + e) = ss[i][e];
+            }
+    }
+    __syncthreads();
+    if (wave == 0) {
+        float* out = partials + (int64_t)blockIdx.x * 3 * d;
+#pragma unroll
+        for (int i = 0; i < CHUNKS; ++i) {
+            const int c = lane + 64 * i;
+            if (c < nchunk)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int col = c * 8 + e;
+                    out[col] = ((sg[i][e] + red(0, 0, col)) + red(1, 0, col)) + red(2, 0, col);
+                    out[d + col] = ((sb[i][e] + red(0, 1, col)) + red(1, 1, col)) + red(2, 1, col);
+                    out[2 * d + col] = ((ss[i][e] + red(0, 2, col)) + red(1, 2, col)) + red(2, 2, col);
+                }
+        }
+    }
+}
+
+// Backward of f = max(0, h): df *= (f > 0) in place on [rows][cols] bf16 (f is the stored output of
+// bias_relu_kernel), and the column sums of the result (the gradient of the bias) of the rows
+// `blockIdx.x, blockIdx.x + gridDim.x, ...` into partials[gridDim.x][cols].  A thread owns up to
+// kReluChunks chunks of 8 columns.
+constexpr int kReluChunks = 4;   // cols <= 8 * 256 * 4
+__global__ void __launch_bounds__(256) relu_bwd_kernel(bf16_t* __restrict__ df, const bf16_t* __restrict__ f,
+                                                       float* __restrict__ partials, int64_t rows, int cols) {
+    const int nchunk = cols >> 3;
+    float acc[kReluChunks][8];
+#pragma unroll
+    for (int i = 0; i < kReluChunks; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[i][e] = 0.f;
+    for (int64_t row = blockIdx.x; row < rows; row += gridDim.x) {
+#pragma unroll
+        for (int i = 0; i < kReluChunks; ++i) {
+            const int c = threadIdx.x + 256 * i;
+            if (c < nchunk) {
+                const int64_t at = row * cols + c * 8;
+                const uint4 gw = *reinterpret_cast<const uint4*>(df + at);
+                const uint4 fw = *reinterpret_cast<const uint4*>(f + at);
+                uint32_t gv[4] = {gw.x, gw.y, gw.z, gw.w};
+                const uint32_t fv[4] = {fw.x, fw.y, fw.z, fw.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    // the stored activations are >= 0: positive iff the bits below the sign are not all zero
+                    if ((fv[e] & 0x7FFFu) == 0u) gv[e] &= 0xFFFF0000u;
+                    if ((fv[e] & 0x7FFF0000u) == 0u) gv[e] &= 0x0000FFFFu;
+                    acc[i][2 * e] += bf16_to_f32(gv[e] & 0xFFFFu);
+                    acc[i][2 * e + 1] += __uint_as_float(gv[e] & 0xFFFF0000u);
+                }
+                *reinterpret_cast<uint4*>(df + at) = make_uint4(gv[0], gv[1], gv[2], gv[3]);
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < kReluChunks; ++i) {
+        const int c = threadIdx.x + 256 * i;
+        if (c < nchunk) {
+            float* out = partials + (int64_t)blockIdx.x * cols + c * 8;
+            *reinterpret_cast<float4*>(out) = make_float4(acc[i][0], acc[i][1], acc[i][2], acc[i][3]);
+            *reinterpret_cast<float4*>(out + 4) = make_float4(acc[i][4], acc[i][5], acc[i][6], acc[i][7]);
+        }
+    }
+}
+
+// Column sums of partials[num_parts][cols] in a fixed order: a workgroup takes 64 columns, its 16
+// wavefronts each sum the rows `w, w + 16, ...` (lane = column, four sums in flight) and the 16 results
+// are added in a fixed tree.  Column c goes to out[c / cols_each][c % cols_each] (up to three outputs
+// whose partial sums sit side by side in a row; a null output is skipped).
+struct ColumnSumOut {
+    float* out[3];
+    int cols_each;
+};
+__global__ void __launch_bounds__(1024) column_sum_kernel(const float* __restrict__ partials, int num_parts, int cols,
+                                                          const ColumnSumOut o) {
+    __shared__ float s[16][64];
+    const int lane = threadIdx.x & 63, grp = threadIdx.x >> 6;
+    const int c = blockIdx.x * 64 + lane;
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    if (c < cols) {
+        const float* src = partials + c;
+        int p = grp;
+        for (; p + 48 < num_parts; p += 64) {
+            s0 += src[(int64_t)p * cols];
+            s1 += src[(int64_t)(p + 16) * cols];
+            s2 += src[(int64_t)(p + 32) * cols];
+            s3 += src[(int64_t)(p + 48) * cols];
+        }
+        for (; p < num_parts; p += 16) s0 += src[(int64_t)p * cols];
+    }
+    s[grp][lane] = (s0 + s1) + (s2 + s3);
+    __syncthreads();
+    for (int w = 8; w > 0; w >>= 1) {
+        if (grp < w) s[grp][lane] += s[grp + w][lane];
+        __syncthreads();
+    }
+    if (grp == 0 && c < cols && o.out[c / o.cols_each]) o.out[c / o.cols_each][c % o.cols_each] = s[0][lane];
+}
+
+// out[i] = sum over s of slices[s][i] in slice order, 4 values per thread: the partial products of a
+// GEMM whose contraction was cut into slices.  Element i belongs to row i / cols; its columns go to
+// out[col / cols_each] (row pitch cols_each): up to three matrices computed side by side.
+__global__ void __launch_bounds__(256) sum_slices_kernel(const float* __restrict__ slices, int num_slices, int64_t elems,
+                                                         int cols, const ColumnSumOut o) {
+    const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (i >= elems) return;
+    float4 acc = *reinterpret_cast<const float4*>(slices + i);
+    for (int sl = 1; sl < num_slices; ++sl) {
+        const float4 x = *reinterpret_cast<const float4*>(slices + (int64_t)sl * elems + i);
+        acc.x += x.x; acc.y += x.y; acc.z += x.z; acc.w += x.w;
+    }
+    const int64_t row = i / cols;
+    const int col = (int)(i - row * cols);
+    *reinterpret_cast<float4*>(o.out[col / o.cols_each] + row * o.cols_each + col % o.cols_each) = acc;
+}
+
+// dst (bf16) [rows][3 d] = src0 | src1 | src2 (fp32, [rows][d] each) side by side, 8 values per thread;
+// blockIdx.y picks the tensor
+struct CastArgs {
+    const float* src[3];
+    bf16_t* dst;
+};
+__global__ void __launch_bounds__(256) cast_bf16_kernel(const CastArgs t, int64_t chunks, int d) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= chunks) return;
+    const float* src = t.src[blockIdx.y] + i * 8;
+    const float4 a = *reinterpret_cast<const float4*>(src), b = *reinterpret_cast<const float4*>(src + 4);
+    const int64_t row = (i * 8) / d;
+    const int col = (int)(i * 8 - row * d);
+    *reinterpret_cast<uint4*>(t.dst + row * 3 * d + (int64_t)blockIdx.y * d + col) =
+        make_uint4(f32_to_bf16(a.x) | (f32_to_bf16(a.y) << 16), f32_to_bf16(a.z) | (f32_to_bf16(a.w) << 16),
+                   f32_to_bf16(b.x) | (f32_to_bf16(b.y) << 16), f32_to_bf16(b.z) | (f32_to_bf16(b.w) << 16));
+}
+
+// y (bf16) = x (bf16) + a (fp32), 8 values per thread
+__global__ void __launch_bounds__(256) add_cast_kernel(const bf16_t* __restrict__ x, const float* __restrict__ a,
+                                                       bf16_t* __restrict__ y, int64_t chunks) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= chunks) return;
+    const uint4 xw = *reinterpret_cast<const uint4*>(x + i * 8);
+    const float4 a0 = *reinterpret_cast<const float4*>(a + i * 8), a1 = *reinterpret_cast<const float4*>(a + i * 8 + 4);
+    const uint32_t w[4] = {xw.x, xw.y, xw.z, xw.w};
+    const float av[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+    uint32_t o[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        o[e] = f32_to_bf16(bf16_to_f32(w[e] & 0xFFFFu) + av[2 * e]) |
+               (f32_to_bf16(__uint_as_float(w[e] & 0xFFFF0000u) + av[2 * e + 1]) << 16);
+    *reinterpret_cast<uint4*>(y + i * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+}
+
 // one rocBLAS handle per device, created on first use
 rocblas_handle blas_handle(int device) {
     static std::mutex mu;
@@ -108,22 +369,29 @@ rocblas_handle blas_handle(int device) {
     return handles[device];
 }
 
-// C[M][N] = A[M][K] B[K][N], row-major, bf16 operands, fp32 accumulation; C bf16 or fp32.
-// rocBLAS is column-major: C^T = B^T A^T with the same buffers.
-int gemm_rm(rocblas_handle h, int64_t M, int N, int K, const void* A, const void* B, void* C, bool c_fp32) {
-    const float one = 1.f, zero = 0.f;
+// C[M][N] = beta C + op(A) op(B), row-major, bf16 operands, fp32 accumulation; C bf16 or fp32.
+// op(A) is [M][K]: A is stored [M][K], or [K][M] with ta; op(B) is [K][N]: B is stored [K][N], or [N][K]
+// with tb.  rocBLAS is column-major: C^T = op(B)^T op(A)^T with the same buffers, a row-major
+// [r][c] buffer being the column-major c x r matrix with leading dimension c.
+int gemm_rm(rocblas_handle h, int64_t M, int64_t N, int64_t K, const void* A, bool ta, const void* B, bool tb, void* C,
+            bool c_fp32, float beta = 0.f, int64_t lda = 0) {   // lda: elements between rows of A as stored (0: dense)
+    const float one = 1.f;
     const rocblas_datatype ct = c_fp32 ? rocblas_datatype_f32_r : rocblas_datatype_bf16_r;
-    const rocblas_status st =
-        rocblas_gemm_ex(h, rocblas_operation_none, rocblas_operation_none, N, (rocblas_int)M, K, &one, B, rocblas_datatype_bf16_r, N,
-                        A, rocblas_datatype_bf16_r, K, &zero, C, ct, N, C, ct, N, rocblas_datatype_f32_r, rocblas_gemm_algo_standard,
-                        0, 0);
+    const rocblas_status st = rocblas_gemm_ex(
+        h, tb ? rocblas_operation_transpose : rocblas_operation_none, ta ? rocblas_operation_transpose : rocblas_operation_none,
+        (rocblas_int)N, (rocblas_int)M, (rocblas_int)K, &one, B, rocblas_datatype_bf16_r, (rocblas_int)(tb ? K : N), A,
+        rocblas_datatype_bf16_r, (rocblas_int)(lda ? lda : (ta ? M : K)), &beta, C, ct, (rocblas_int)N, C, ct, (rocblas_int)N,
+        rocblas_datatype_f32_r, rocblas_gemm_algo_standard, 0, 0);
     return st == rocblas_status_success ? BPT_OK : BPT_ERR_LAUNCH;
+}
+int gemm_rm(rocblas_handle h, int64_t M, int N, int K, const void* A, const void* B, void* C, bool c_fp32) {
+    return gemm_rm(h, M, N, K, A, false, B, false, C, c_fp32);
 }
 
 size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct LayerBuffers {
-    size_t q, k, v, o, lse, acc, z, f1, attn, total;
+    size_t q, k, v, o, lse, acc1, acc2, st1, st2, z, f1, attn, total;
 };
 LayerBuffers layer_buffers(const bpt_graph* g, int B, int H, int d_ff, size_t attn_ws) {
     const size_t rows = (size_t)B * g->num_nodes, d = (size_t)H * kD;
@@ -139,7 +407,10 @@ LayerBuffers layer_buffers(const bpt_graph* g, int B, int H, int d_ff, size_t at
     L.v = take(rows * d * 2);
     L.o = take(rows * d * 2);
     L.lse = take((size_t)B * H * g->num_nodes * 4);
-    L.acc = take(rows * d * 4);      // W^O and W_2 results, fp32
+    L.acc1 = take(rows * d * 4);     // W^O result, fp32
+    L.acc2 = take(rows * d * 4);     // W_2 result, fp32
+    L.st1 = take(rows * sizeof(float2));   // (mean, 1/deviation) of the two normalisations
+    L.st2 = take(rows * sizeof(float2));
     L.z = take(rows * d * 2);
     L.f1 = take(rows * (size_t)d_ff * 2);
     L.attn = take(attn_ws);
@@ -159,6 +430,108 @@ bpt_shape_t attn_shape(const bpt_graph* g, int B, int H, float scale, const int3
     s.scale = scale;
     s.seq_len = seq_len;
     return s;
+}
+
+// slices of the contraction over K for an M x N result: enough to give every compute unit a tile
+int pick_slices(int M, int N, int64_t K) {
+    const int64_t tiles = (int64_t)((M + 127) / 128) * ((N + 127) / 128);
+    const int64_t want = (512 + tiles - 1) / tiles;
+    return (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(want, 16), K / 2048));
+}
+
+constexpr int kColumnSumBlocks = 2048;   // workgroups (= partial rows) of the kernels that sum over rows
+
+struct LayerBwdBuffers {
+    size_t ds2, dh, t, ds1, da, dq, dk, dv, dqkv, part, gw, attn, total;
+};
+LayerBwdBuffers layer_bwd_buffers(const bpt_graph* g, int B, int H, int d_ff, size_t attn_ws) {
+    const size_t rows = (size_t)B * g->num_nodes, d = (size_t)H * kD;
+    LayerBwdBuffers L;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        const size_t at = off;
+        off += align_up(bytes);
+        return at;
+    };
+    L.ds2 = take(rows * d * 2);              // gradient of the second pre-normalisation sum, bf16
+    L.dh = take(rows * (size_t)d_ff * 2);    // gradient of the hidden FFN activations, bf16
+    L.t = take(rows * d * 4);                // fp32 GEMM results: dH W1^T, later dQ Wq^T + dK Wk^T + dV Wv^T
+    L.ds1 = take(rows * d * 2);
+    L.da = take(rows * d * 2);               // gradient of the attention output, [B][N][H][64] bf16
+    L.dq = take(rows * d * 4);               // the attention's fp32 gradients ...
+    L.dk = take(rows * d * 4);
+    L.dv = take(rows * d * 4);
+    L.dqkv = take(rows * 3 * d * 2);         // ... and their bf16 copies side by side, [rows][3 d], for the projections
+    L.part = take((size_t)kColumnSumBlocks * std::max<size_t>(3 * d, (size_t)d_ff) * 4);
+    // partial products of the weight gradients (contraction over the rows, cut into slices)
+    const size_t gw_qkv = (size_t)pick_slices((int)d, (int)(3 * d), (int64_t)rows) * d * 3 * d;
+    const size_t gw_ffn = (size_t)pick_slices((int)d, d_ff, (int64_t)rows) * d * (size_t)d_ff;
+    const size_t gw_o = (size_t)pick_slices((int)d, (int)d, (int64_t)rows) * d * d;
+    L.gw = take(std::max(gw_qkv, std::max(gw_ffn, gw_o)) * 4);
+    L.attn = take(attn_ws);
+    L.total = off;
+    return L;
+}
+
+// column sums of partials[parts][cols]; the columns are `cols / cols_each` outputs side by side
+template <int CHUNKS>
+int launch_ln_bwd_as(int blocks, hipStream_t st, const bf16_t* dy_b, const float* dy_f, const bf16_t* x, const float* a,
+                     const float* bias, const float* gain, const float2* stats, bf16_t* ds, float* partials, int64_t rows, int d,
+                     const int32_t* seq_len, int N, int lg) {
+    const size_t lds = (size_t)9 * d * sizeof(float);
+    if (lds > 65536)
+        BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(layer_norm_bwd_kernel<CHUNKS>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    BPT_LAUNCH("layer_norm_bwd_kernel", layer_norm_bwd_kernel<CHUNKS>, dim3(blocks), dim3(256), lds, st, dy_b, dy_f, x, a, bias,
+               gain, stats, ds, partials, rows, d, seq_len, N, lg);
+    BPT_HIP(hipGetLastError());
+    return BPT_OK;
+}
+template <typename... Args>
+int launch_ln_bwd(int d, Args... args) {
+    if (d <= 512) return launch_ln_bwd_as<1>(args...);
+    if (d <= 1024) return launch_ln_bwd_as<2>(args...);
+    return launch_ln_bwd_as<kLnMaxChunks>(args...);
+}
+
+int column_sum(const float* partials, int parts, int cols, int cols_each, float* o0, float* o1, float* o2, hipStream_t st) {
+    const ColumnSumOut o = {{o0, o1, o2}, cols_each};
+    BPT_LAUNCH("column_sum_kernel", column_sum_kernel, dim3((cols + 63) / 64), dim3(1024), 0, st, partials, parts, cols, o);
+    BPT_HIP(hipGetLastError());
+    return BPT_OK;
+}
+
+// C[M][N] (fp32) = A^T B with A stored [K][M], B stored [K][N], bf16, K long and M x N small: the
+// contraction is cut into `slices` equal parts that run as one strided-batched GEMM into
+// `partials` [slices][M][N] (plus the few left-over rows of K into the first part), and the parts
+// are added in slice order by sum_slices_kernel.  The N columns are N / n_each matrices side by
+// side that go to out0..out2 (each [M][n_each]).
+int gemm_at_b_sliced(rocblas_handle h, int M, int N, int64_t K, const void* A, const void* B, int ldb_cols, float* partials,
+                     int slices, int n_each, float* out0, float* out1, float* out2, hipStream_t st) {
+    const float one = 1.f, zero = 0.f;
+    const int64_t ks = K / slices;
+    if (ks < 1) return BPT_ERR_INVALID_ARG;
+    // column-major view: C^T (N x M) = B^T-as-stored (N x K, ld = ldb_cols) times A (K x M) given as its transpose
+    rocblas_status rs = rocblas_gemm_strided_batched_ex(
+        h, rocblas_operation_none, rocblas_operation_transpose, N, M, (rocblas_int)ks, &one, B, rocblas_datatype_bf16_r, ldb_cols,
+        ks * ldb_cols, A, rocblas_datatype_bf16_r, M, ks * (int64_t)M, &zero, partials, rocblas_datatype_f32_r, N, (int64_t)M * N,
+        partials, rocblas_datatype_f32_r, N, (int64_t)M * N, slices, rocblas_datatype_f32_r, rocblas_gemm_algo_standard, 0, 0);
+    if (rs != rocblas_status_success) return BPT_ERR_LAUNCH;
+    const int64_t done = ks * slices;
+    if (done < K) {
+        rs = rocblas_gemm_ex(h, rocblas_operation_none, rocblas_operation_transpose, N, M, (rocblas_int)(K - done), &one,
+                             static_cast<const bf16_t*>(B) + done * ldb_cols, rocblas_datatype_bf16_r, ldb_cols,
+                             static_cast<const bf16_t*>(A) + done * M, rocblas_datatype_bf16_r, M, &one, partials,
+                             rocblas_datatype_f32_r, N, partials, rocblas_datatype_f32_r, N, rocblas_datatype_f32_r,
+                             rocblas_gemm_algo_standard, 0, 0);
+        if (rs != rocblas_status_success) return BPT_ERR_LAUNCH;
+    }
+    const ColumnSumOut o = {{out0, out1, out2}, n_each};
+    const int64_t elems = (int64_t)M * N;
+    BPT_LAUNCH("sum_slices_kernel", sum_slices_kernel, dim3((unsigned)((elems / 4 + 255) / 256)), dim3(256), 0, st, partials,
+               slices, elems, N, o);
+    BPT_HIP(hipGetLastError());
+    return BPT_OK;
 }
 
 }  // namespace
@@ -193,7 +566,10 @@ int bpt_layer_fwd(const bpt_graph_t* g, int32_t B, int32_t H, float scale, const
     unsigned char* ws = static_cast<unsigned char*>(workspace);
     void *q = ws + L.q, *k = ws + L.k, *v = ws + L.v, *o = ws + L.o, *z = ws + L.z, *f1 = ws + L.f1;
     float* lse = reinterpret_cast<float*>(ws + L.lse);
-    float* acc = reinterpret_cast<float*>(ws + L.acc);
+    float* acc1 = reinterpret_cast<float*>(ws + L.acc1);
+    float* acc2 = reinterpret_cast<float*>(ws + L.acc2);
+    float2* st1 = reinterpret_cast<float2*>(ws + L.st1);
+    float2* st2 = reinterpret_cast<float2*>(ws + L.st2);
     const float eps = p->eps > 0.f ? p->eps : 1e-5f;
     int rc;
     // Q, K, V = X Wq, X Wk, X Wv for all nodes: [B][N][H][64], the layout the attention reads through its strides
@@ -202,11 +578,11 @@ int bpt_layer_fwd(const bpt_graph_t* g, int32_t B, int32_t H, float scale, const
         return rc;
     if ((rc = bpt_attn_fwd(g, &s, q, k, v, rel, o, lse, ws + L.attn, attn_ws, stream))) return rc;
     // Z = norm(X + O Wo)
-    if ((rc = gemm_rm(h, rows, d, d, o, p->Wo, acc, true))) return rc;
+    if ((rc = gemm_rm(h, rows, d, d, o, p->Wo, acc1, true))) return rc;
     const unsigned ln_blocks = (unsigned)((rows + 3) / 4);
     BPT_LAUNCH("residual_layer_norm_kernel", residual_layer_norm_kernel, dim3(ln_blocks), dim3(256), 0, st,
-               static_cast<const bf16_t*>(X), acc, static_cast<const float*>(nullptr), p->g1, p->beta1, static_cast<bf16_t*>(z), rows,
-               d, eps);
+               static_cast<const bf16_t*>(X), acc1, static_cast<const float*>(nullptr), p->g1, p->beta1, static_cast<bf16_t*>(z),
+               st1, rows, d, eps);
     BPT_HIP(hipGetLastError());
     // Y = norm(Z + max(0, Z W1 + b1) W2 + b2)
     if ((rc = gemm_rm(h, rows, d_ff, d, z, p->W1, f1, false))) return rc;
@@ -214,9 +590,102 @@ int bpt_layer_fwd(const bpt_graph_t* g, int32_t B, int32_t H, float scale, const
     BPT_LAUNCH("bias_relu_kernel", bias_relu_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st,
                static_cast<bf16_t*>(f1), p->b1, chunks, d_ff);
     BPT_HIP(hipGetLastError());
-    if ((rc = gemm_rm(h, rows, d, d_ff, f1, p->W2, acc, true))) return rc;
+    if ((rc = gemm_rm(h, rows, d, d_ff, f1, p->W2, acc2, true))) return rc;
     BPT_LAUNCH("residual_layer_norm_kernel", residual_layer_norm_kernel, dim3(ln_blocks), dim3(256), 0, st,
-               static_cast<const bf16_t*>(z), acc, p->b2, p->g2, p->beta2, static_cast<bf16_t*>(Y), rows, d, eps);
+               static_cast<const bf16_t*>(z), acc2, p->b2, p->g2, p->beta2, static_cast<bf16_t*>(Y), st2, rows, d, eps);
+    BPT_HIP(hipGetLastError());
+    return BPT_OK;
+}
+
+size_t bpt_layer_bwd_workspace(const bpt_graph_t* g, int32_t B, int32_t H, int32_t d_ff) {
+    if (!g || B < 1 || H < 1 || d_ff < 8) return 0;
+    const bpt_shape_t s = attn_shape(g, B, H, 0.f, nullptr);
+    return layer_bwd_buffers(g, B, H, d_ff, bpt_attn_bwd_workspace(g, &s)).total;
+}
+
+int bpt_layer_bwd(const bpt_graph_t* g, int32_t B, int32_t H, float scale, const int32_t* seq_len, const void* rel,
+                  const void* X, const bpt_layer_params_t* p, const void* fwd_workspace, size_t fwd_workspace_bytes,
+                  const void* dY, void* dX, float* d_rel, const bpt_layer_grads_t* gr, void* workspace,
+                  size_t workspace_bytes, void* stream) {
+    if (!g || !rel || !X || !p || !fwd_workspace || !dY || !dX || !d_rel || !gr || B < 1 || H < 1) return BPT_ERR_INVALID_ARG;
+    if (!p->Wq || !p->Wk || !p->Wv || !p->Wo || !p->W1 || !p->W2 || !p->b1 || !p->b2 || !p->g1 || !p->beta1 || !p->g2 || !p->beta2)
+        return BPT_ERR_INVALID_ARG;
+    if (!gr->dWq || !gr->dWk || !gr->dWv || !gr->dWo || !gr->dW1 || !gr->db1 || !gr->dW2 || !gr->db2 || !gr->dg1 ||
+        !gr->dbeta1 || !gr->dg2 || !gr->dbeta2)
+        return BPT_ERR_INVALID_ARG;
+    const int d = H * kD, d_ff = p->d_ff;
+    if (d > 8 * 64 * kLnMaxChunks || d_ff < 8 || (d_ff & 7) || d_ff > 8 * 256 * kReluChunks) return BPT_ERR_UNSUPPORTED;
+    const int64_t rows = (int64_t)B * g->num_nodes;
+    if (rows > INT32_MAX) return BPT_ERR_UNSUPPORTED;
+    const bpt_shape_t s = attn_shape(g, B, H, scale, seq_len);
+    const LayerBuffers F = layer_buffers(g, B, H, d_ff, bpt_attn_fwd_workspace(g, &s));
+    if (F.total > fwd_workspace_bytes) return BPT_ERR_INVALID_ARG;
+    const size_t attn_ws = bpt_attn_bwd_workspace(g, &s);
+    const LayerBwdBuffers L = layer_bwd_buffers(g, B, H, d_ff, attn_ws);
+    if (L.total > workspace_bytes || !workspace) return BPT_ERR_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    rocblas_handle h = blas_handle(g->device);
+    if (!h || rocblas_set_stream(h, st) != rocblas_status_success) return BPT_ERR_LAUNCH;
+    const unsigned char* fw = static_cast<const unsigned char*>(fwd_workspace);
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    const void *q = fw + F.q, *k = fw + F.k, *v = fw + F.v, *o = fw + F.o;
+    const bf16_t* z = reinterpret_cast<const bf16_t*>(fw + F.z);
+    const bf16_t* f1 = reinterpret_cast<const bf16_t*>(fw + F.f1);
+    const float* lse = reinterpret_cast<const float*>(fw + F.lse);
+    const float *acc1 = reinterpret_cast<const float*>(fw + F.acc1), *acc2 = reinterpret_cast<const float*>(fw + F.acc2);
+    const float2 *st1 = reinterpret_cast<const float2*>(fw + F.st1), *st2 = reinterpret_cast<const float2*>(fw + F.st2);
+    bf16_t *ds2 = reinterpret_cast<bf16_t*>(ws + L.ds2), *dh = reinterpret_cast<bf16_t*>(ws + L.dh);
+    bf16_t *ds1 = reinterpret_cast<bf16_t*>(ws + L.ds1), *da = reinterpret_cast<bf16_t*>(ws + L.da);
+    float *t = reinterpret_cast<float*>(ws + L.t), *part = reinterpret_cast<float*>(ws + L.part);
+    float *dq = reinterpret_cast<float*>(ws + L.dq), *dk = reinterpret_cast<float*>(ws + L.dk), *dv = reinterpret_cast<float*>(ws + L.dv);
+    bf16_t* dqkv = reinterpret_cast<bf16_t*>(ws + L.dqkv);
+    float* gw = reinterpret_cast<float*>(ws + L.gw);
+    const int lg = 31 - __builtin_clz((unsigned)g->n);
+    const int ln_blocks = (int)std::min<int64_t>(kColumnSumBlocks, (rows + 3) / 4);
+    const bf16_t* Xb = static_cast<const bf16_t*>(X);
+    int rc;
+
+    // second normalisation: dS2 (= the gradient of Z's residual branch, of the FFN output and of b2), dg2, dbeta2
+    if ((rc = launch_ln_bwd(d, ln_blocks, st, static_cast<const bf16_t*>(dY), static_cast<const float*>(nullptr), z, acc2, p->b2,
+                            p->g2, st2, ds2, part, rows, d, seq_len, g->num_nodes, lg)))
+        return rc;
+    if ((rc = column_sum(part, ln_blocks, 3 * d, d, gr->dg2, gr->dbeta2, gr->db2, st))) return rc;
+    // FFN: dW2 = F^T dS2, dH = (dS2 W2^T) where the hidden unit was active, db1, dW1 = Z^T dH
+    if ((rc = gemm_at_b_sliced(h, d_ff, d, rows, f1, ds2, d, gw, pick_slices(d, d_ff, rows), d, gr->dW2, nullptr, nullptr, st)))
+        return rc;
+    if ((rc = gemm_rm(h, rows, d_ff, d, ds2, false, p->W2, true, dh, false))) return rc;
+    const int relu_blocks = (int)std::min<int64_t>(kColumnSumBlocks, rows);
+    BPT_LAUNCH("relu_bwd_kernel", relu_bwd_kernel, dim3(relu_blocks), dim3(256), 0, st, dh, f1, part, rows, d_ff);
+    BPT_HIP(hipGetLastError());
+    if ((rc = column_sum(part, relu_blocks, d_ff, d_ff, gr->db1, nullptr, nullptr, st))) return rc;
+    if ((rc = gemm_at_b_sliced(h, d, d_ff, rows, z, dh, d_ff, gw, pick_slices(d, d_ff, rows), d_ff, gr->dW1, nullptr, nullptr, st)))
+        return rc;
+    if ((rc = gemm_rm(h, rows, d, d_ff, dh, false, p->W1, true, t, true))) return rc;
+    // first normalisation with dZ = dS2 + dH W1^T: dS1 (= the gradient of X's residual branch and of the
+    // attention sublayer's output), dg1, dbeta1 (the third column sum, that of dS1, belongs to no parameter)
+    if ((rc = launch_ln_bwd(d, ln_blocks, st, static_cast<const bf16_t*>(ds2), static_cast<const float*>(t), Xb, acc1,
+                            static_cast<const float*>(nullptr), p->g1, st1, ds1, part, rows, d,
+                            static_cast<const int32_t*>(nullptr), g->num_nodes, lg)))
+        return rc;
+    if ((rc = column_sum(part, ln_blocks, 3 * d, d, gr->dg1, gr->dbeta1, nullptr, st))) return rc;
+    // attention sublayer: dWo = O^T dS1, dO = dS1 Wo^T, then the attention's own backward
+    if ((rc = gemm_at_b_sliced(h, d, d, rows, o, ds1, d, gw, pick_slices(d, d, rows), d, gr->dWo, nullptr, nullptr, st))) return rc;
+    if ((rc = gemm_rm(h, rows, d, d, ds1, false, p->Wo, true, da, false))) return rc;
+    if ((rc = bpt_attn_bwd(g, &s, q, k, v, rel, lse, da, dq, dk, dv, d_rel, ws + L.attn, attn_ws, stream))) return rc;
+    const CastArgs ca = {{dq, dk, dv}, dqkv};
+    const int64_t chunks = rows * d / 8;
+    BPT_LAUNCH("cast_bf16_kernel", cast_bf16_kernel, dim3((unsigned)((chunks + 255) / 256), 3), dim3(256), 0, st, ca, chunks, d);
+    BPT_HIP(hipGetLastError());
+    // projections: [dWq | dWk | dWv] = X^T [dQ | dK | dV] in one product, dX = dS1 + dQ Wq^T + dK Wk^T + dV Wv^T
+    if ((rc = gemm_at_b_sliced(h, d, 3 * d, rows, X, dqkv, 3 * d, gw, pick_slices(d, 3 * d, rows), d, gr->dWq, gr->dWk, gr->dWv,
+                               st)))
+        return rc;
+    if ((rc = gemm_rm(h, rows, d, d, dqkv, false, p->Wq, true, t, true, 0.f, 3 * d)) ||
+        (rc = gemm_rm(h, rows, d, d, dqkv + d, false, p->Wk, true, t, true, 1.f, 3 * d)) ||
+        (rc = gemm_rm(h, rows, d, d, dqkv + 2 * d, false, p->Wv, true, t, true, 1.f, 3 * d)))
+        return rc;
+    BPT_LAUNCH("add_cast_kernel", add_cast_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st,
+               static_cast<const bf16_t*>(ds1), static_cast<const float*>(t), static_cast<bf16_t*>(dX), chunks);
     BPT_HIP(hipGetLastError());
     return BPT_OK;
 }

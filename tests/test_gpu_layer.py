@@ -71,3 +71,73 @@ def test_layer_forward(n, k, causal, B, heads, d_ff, zero_spans, lengths):
     print("   max-abs error %.3g, |Y| max %.3g" % (err, np.abs(ref).max()), flush=True)
     assert err <= TOL, err
     g.destroy()
+
+
+# ---------------------------------------------------------------------------------- backward
+# Tolerance of the backward.  Every gradient is compared as max-abs error relative to the largest entry of
+# the oracle's tensor: gradients of parameters are sums over all node rows and have no natural absolute
+# scale.  Between the dense maps every activation and every gradient is rounded to bf16 once (2^-9
+# relative, independent) and the stored activations differ from the oracle's by the forward's error.
+#
+# The gate of the ReLU is a decision taken from floating-point values: a hidden unit whose pre-activation
+# lies within the forward's error of zero can be on in the kernel and off in the oracle.  A flipped unit
+# changes its gradient by all of it, not by a rounding error; with a fraction f of flipped units the sums
+# over them (db1, dW1, and everything downstream of the FFN branch: dX, the attention's gradients) are off
+# by about sqrt(f) of their size -- measured 3..10 % with N(0, 0.1^2) biases, where f is about 0.3 %.
+# So the cases come in two kinds:
+#  * `decisive`: b1 = +6 or -6 by column, which puts every pre-activation (unit variance) six deviations
+#    from zero; both sides then take the same gate, half of the units on, and what remains is rounding:
+#    measured 0.1..0.6 % of the largest entry, bound 1.5 %;
+#  * ordinary biases: the same comparison with the bound 15 %, which still separates a correct backward
+#    from a wrong operand, transpose or sign (those give errors of the order of the tensor itself).
+from oracle.layer import kept_rows, layer_backward   # noqa: E402
+
+BWD_TOL_DECISIVE, BWD_TOL_ORDINARY = 1.5e-2, 15e-2
+GRADS = ("dWq", "dWk", "dWv", "dWo", "dW1", "db1", "dW2", "db2", "dg1", "dbeta1", "dg2", "dbeta2")
+
+
+@pytest.mark.parametrize("n,k,causal,B,heads,d_ff,lengths,decisive", [
+    (64, 2, False, 2, 1, 64, None, True), (256, 4, True, 2, 2, 256, None, True), (512, 4, False, 2, 8, 2048, None, True),
+    (256, 3, False, 3, 4, 512, [256, 150, 31], True), (1024, 8, True, 1, 8, 1024, None, True),
+    (256, 4, True, 2, 2, 256, None, False), (256, 3, False, 3, 4, 512, [256, 150, 31], False),
+])
+def test_layer_backward(n, k, causal, B, heads, d_ff, lengths, decisive):
+    print("layer backward", n, k, causal, B, heads, d_ff, lengths, decisive, flush=True)
+    X, Rel, p = make_case(n, k, causal, B, heads, d_ff, 300 + n + heads, False)
+    if decisive:
+        p["b1"] = np.where(np.arange(d_ff) % 2 == 0, 6.0, -6.0).astype(np.float32)
+    rng = np.random.Generator(np.random.PCG64(77 + n))
+    dY = round_to_bf16(rng.standard_normal(X.shape).astype(np.float32))[0]
+    g = bpt.bpt_build_graph(n, k, causal)
+    lens_d = torch.tensor(lengths, dtype=torch.int32, device="cuda") if lengths else None
+    fws, bws = bpt.layer_workspace_bytes(g, B, heads, d_ff)
+    ws_f = torch.empty(fws + 256, dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(bws + 256, dtype=torch.uint8, device="cuda")
+    Xd, Rd, pd = torch.from_numpy(X).to(torch.bfloat16).cuda(), torch.from_numpy(Rel).to(torch.bfloat16).cuda(), to_dev(p)
+    bpt.bpt_layer_fwd(g, Xd, Rd, pd, heads, scale=0.125, seq_len=lens_d, workspace=ws_f)
+    dX, d_rel, grads = bpt.bpt_layer_bwd(g, Xd, Rd, pd, heads, ws_f, torch.from_numpy(dY).to(torch.bfloat16).cuda(),
+                                         scale=0.125, seq_len=lens_d, workspace=ws_b)
+    torch.cuda.synchronize()
+    ref = layer_backward(n, k, causal, heads, X, Rel, p, dY, 0.125, lengths=lengths)
+    got = {"dX": dX, "dRel": d_rel}
+    got.update(grads)
+    worst = {}
+    for name in ("dX", "dRel") + GRADS:
+        a = got[name].float().cpu().numpy().astype(np.float64)
+        assert np.isfinite(a).all(), name
+        top = float(np.abs(ref[name]).max())
+        worst[name] = float(np.abs(a - ref[name]).max()) / max(top, 1e-30)
+    print("   relative max-abs errors", {k_: float("%.2g" % v) for k_, v in worst.items()}, flush=True)
+    tol = BWD_TOL_DECISIVE if decisive else BWD_TOL_ORDINARY
+    for name, v in worst.items():
+        assert v <= tol, (name, v)
+    if lengths:   # rows of nodes a sequence does not keep get exactly no gradient
+        gone = torch.from_numpy(~kept_rows(n, lengths)).cuda()
+        assert float(dX.float()[gone].abs().max()) == 0.0
+    # a second call with the same arguments gives the same bits (fixed-order sums; no atomics of ours)
+    dX2, d_rel2, grads2 = bpt.bpt_layer_bwd(g, Xd, Rd, pd, heads, ws_f, torch.from_numpy(dY).to(torch.bfloat16).cuda(),
+                                            scale=0.125, seq_len=lens_d, workspace=ws_b)
+    assert torch.equal(dX, dX2) and torch.equal(d_rel, d_rel2)
+    for name in ("db1", "db2", "dg1", "dbeta1", "dg2", "dbeta2"):
+        assert torch.equal(grads[name], grads2[name]), name
+    g.destroy()
