@@ -47,6 +47,7 @@ struct AttnArgs {
     // dropout on the attention weights: an edge is kept iff its hash >= drop_thr (0: no dropout)
     uint32_t drop_thr, drop_seed;
     float drop_inv_keep;    // 1 / (1 - p)
+    int32_t* queue;         // backward workspace: task counters of the key-tile kernel
 };
 
 // ---- dropout on the attention weights ---------------------------------------------------

@@ -38,7 +38,14 @@ struct KeyArgs {
     int32_t n;
     uint32_t drop_thr, drop_seed;   // dropout on the attention weights (DROP variants)
     float drop_inv_keep;
+    int32_t* queue;   // 8 task counters (one per XCD, 64 bytes apart), zero when the kernel starts
 };
+
+// `count` ints = 0 (the task counters of bwd_kv_tile_kernel; a fill kernel, so that the call can be captured in a graph)
+__global__ void zero_ints_kernel(int32_t* p, int count) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) p[i] = 0;
+}
 
 template <int NBC, bool DROP>
 __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyArgs a) {
@@ -67,15 +74,26 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyA
                                                                         32 * sizeof(uint32_t))) +
                   ((size_t)wave * (kParked > 0 ? kParked : 1) * 64 + lane) * 2;
     const float qscale = a.scale * kLog2e;
-    const int groups = (a.num_tasks + kTileWaves - 1) / kTileWaves;
+    // The (batch*head, task) space is split into 8 contiguous shares, one per XCD (workgroup w runs on
+    // XCD w mod 8).  The wavefronts of an XCD take the tasks of its share in order from a shared counter:
+    // tasks differ 16-fold in length, and with a fixed assignment the wavefronts drift apart until the XCD
+    // works on many (batch, head)s at once and their rows push each other out of its L2.  Taken in order,
+    // the wavefronts stay within a few hundred consecutive tasks.  Which wavefront computes a task changes
+    // no result.
+    const int xcd = blockIdx.x & 7;
+    const int total = a.BH * a.num_tasks, per = (total + 7) >> 3;
+    const int share_begin = xcd * per, share_end = min(total, share_begin + per);
     const rsrc_t rC = make_rsrc(a.cols, (uint32_t)a.num_chunks * 64u);    // [chunks][16] int32
     const rsrc_t rM = make_rsrc(a.map, (uint32_t)a.num_chunks * 512u);    // [chunks][16][16] int16
 
-    for (TileWalk w(a.BH * groups); w.t < w.t_end; w.t += w.step) {
-        const int slab = w.t / groups;
+    for (;;) {
+        int item = 0;
+        if (lane == 0) item = atomicAdd(a.queue + xcd * 16, 1);
+        item = __builtin_amdgcn_readfirstlane(item) + share_begin;
+        if (item >= share_end) break;   // every wavefront gets here: the counter only grows
+        const int slab = item / a.num_tasks;
         const int bh = walk_bh(a.seq_len, slab, a.BH, a.H);
-        const int task = walk_pos(a.seq_len, slab, w.t - slab * groups, groups) * kTileWaves + wave;
-        if (task >= a.num_tasks) continue;
+        const int task = item - slab * a.num_tasks;
         const int kt = uniform_i32(a.task_tile, task), c0 = uniform_i32(a.task_c0, task), part = uniform_i32(a.task_part, task);
         const int node0 = uniform_i32(a.tile_node0, kt), info = uniform_i32(a.tile_info, kt);
         const int level = info & 255, nkeys = info >> 8;

@@ -351,6 +351,7 @@ int run_fwd(const bpt_graph* g, AttnArgs& a, hipStream_t st) {
 }
 
 // Workspace layout of the backward and the launch shape of rel_grad_kernel.
+constexpr int kQueueInts = 8 * 16;   // one counter per XCD, 64 bytes apart
 struct BwdPlan {
     int drel_rows = 0;        // d_rel rows token rows can touch
     bool drel_mfma = false;   // bf16 tensors: rel_grad_mfma_kernel; fp32: rel_grad_kernel
@@ -363,7 +364,7 @@ struct BwdPlan {
     int drel_block = 32;      // token rows per block
     int drel_grid_x = 8, drel_grid_y = 1;
     size_t drel_lds = 0;
-    size_t off_stat = 0, off_wp = 0, off_qpart = 0, off_kvpart = 0, off_drel = 0, total = 0;
+    size_t off_stat = 0, off_wp = 0, off_qpart = 0, off_kvpart = 0, off_drel = 0, off_queue = 0, total = 0;
 };
 
 int plan_bwd(const bpt_graph* g, const bpt_shape_t* s, BwdPlan* p) {
@@ -419,6 +420,8 @@ int plan_bwd(const bpt_graph* g, const bpt_shape_t* s, BwdPlan* p) {
     p->off_drel = off;
     if (!p->drel_tile) p->drel_part_rows = p->drel_rows;
     off += align_up((size_t)p->drel_grid_x * p->drel_part_rows * kD * sizeof(float));
+    p->off_queue = off;
+    off += align_up(kQueueInts * sizeof(int32_t));   // task counters of the key-tile kernel
     p->total = off;
     return BPT_OK;
 }
@@ -588,6 +591,10 @@ int run_bwd_kv_tiles(const bpt_graph* g, const BwdPlan& p, const AttnArgs& a, co
     t.drop_thr = a.drop_thr;
     t.drop_seed = a.drop_seed;
     t.drop_inv_keep = a.drop_inv_keep;
+    t.queue = a.queue;
+    if ((int64_t)a.BH * kt.num_tasks > INT32_MAX) return BPT_ERR_UNSUPPORTED;
+    BPT_LAUNCH("zero_ints_kernel", zero_ints_kernel, dim3(1), dim3(kQueueInts), 0, st, t.queue, kQueueInts);
+    BPT_HIP(hipGetLastError());
     int rc = BPT_ERR_UNSUPPORTED;
     switch (kt.nb_pad / 16) {
         case 1: rc = launch_kv_tiles<1>(t, p, lim, st); break;
@@ -679,6 +686,7 @@ int backward(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q, const vo
     a.wp = reinterpret_cast<float2*>(ws + p.off_wp);
     a.e_tok = g->num_token_edges;
     a.drel_part = reinterpret_cast<float*>(ws + p.off_drel);
+    a.queue = reinterpret_cast<int32_t*>(ws + p.off_queue);
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool bf = s->dtype == BPT_BF16;
     if (stages & kStageQ) {
