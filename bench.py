@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
 # workload; the runs and their commands are in profiles/.  None where not measured.
 MEASURED_TRAFFIC = {
     "lm": {  # profiles/lm_n8192_k8_causal_bf16_kernels.md
-        "bwd_kv_tile_kernel": int((322754.0 * 2.0 + 278784.0) * 1024),
+        "bwd_kv_tile_kernel": int((223979.5 * 2.0 + 279937.0) * 1024),
         "bwd_q_tile_kernel": int((144196.4 * 2.0 + 309269.9) * 1024),
         "rel_grad_tile_kernel": int((173082.0 * 2.0 + 90112.3) * 1024),
         "fwd_tile_kernel": int((117065.4 * 2.0 + 33873.9) * 1024),
@@ -36,7 +36,7 @@ MEASURED_TRAFFIC = {
     },
 }
 # HBM bytes of one whole step (all kernels, same counters and scaling)
-MEASURED_STEP_TRAFFIC = {"lm": 2784974950}
+MEASURED_STEP_TRAFFIC = {"lm": 2584055600}
 
 
 def parse():

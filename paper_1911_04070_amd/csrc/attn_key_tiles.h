@@ -90,7 +90,8 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyA
         int item = 0;
         if (lane == 0) item = atomicAdd(a.queue + xcd * 16, 1);
         item = __builtin_amdgcn_readfirstlane(item) + share_begin;
-        if (item >= share_end) break;   // every wavefront gets here: the counter only grows
+        // every wavefront gets here: the counter only grows from zero
+        if (item >= share_end) break;
         const int slab = item / a.num_tasks;
         const int bh = walk_bh(a.seq_len, slab, a.BH, a.H);
         const int task = item - slab * a.num_tasks;

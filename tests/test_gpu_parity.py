@@ -405,3 +405,47 @@ def test_invalid_arguments_on_device():
         bpt.bpt_attn_fwd(g, Q32, Q32, Q32, R32)
     assert e.value.status == bpt.BPT_ERR_UNSUPPORTED
     g.destroy()
+
+
+def test_forward_and_backward_replay_from_a_captured_graph():
+    # the calls only launch kernels on the caller's stream (no allocation, no synchronisation, no memset
+    # node), so a step can be captured once and replayed: every replay, with new inputs in the same
+    # buffers and eager work of the program in between, gives the bits of the eager call
+    w = Workload("capture", 27, 2048, 4, True, 2, 2, 64, "bf16", True)
+    g = bpt.bpt_build_graph(w.n, w.k, w.causal)
+    x = make_inputs(w)
+    Q, K, V, dO, R = (to_dev(x[k_], "bf16") for k_ in ("Q", "K", "V", "dO", "Rel"))
+    out = torch.empty_like(Q)
+    lse = torch.empty(Q.shape[:3], dtype=torch.float32, device="cuda")
+    grads = tuple(torch.empty(Q.shape, dtype=torch.float32, device="cuda") for _ in range(3)) + (
+        torch.empty(R.shape, dtype=torch.float32, device="cuda"),)
+    fws, bws = bpt.workspace_bytes(g, Q, w.scale)
+    ws_f = torch.empty(max(fws, 256), dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(max(bws, 256), dtype=torch.uint8, device="cuda")
+
+    def step():
+        bpt.bpt_attn_fwd(g, Q, K, V, R, scale=w.scale, out=out, lse=lse, workspace=ws_f)
+        bpt.bpt_attn_bwd(g, Q, K, V, R, lse, dO, scale=w.scale, grads=grads, workspace=ws_b)
+
+    step()                                   # first use of every kernel outside the capture
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        step()
+        graph.capture_end()
+    torch.cuda.synchronize()
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    for replay in range(3):
+        for t in (Q, K, V, dO):              # new inputs in the captured buffers
+            t.copy_(torch.randn(t.shape, device="cuda", generator=gen).to(t.dtype))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [out.clone(), lse.clone()] + [t.clone() for t in grads]
+        step()                               # eager, same buffers
+        torch.cuda.synchronize()
+        for name, a, b in zip(("out", "lse", "dQ", "dK", "dV", "d_rel"), got, [out, lse] + list(grads)):
+            assert torch.equal(a, b), (replay, name)
+    g.destroy()
