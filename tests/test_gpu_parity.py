@@ -39,7 +39,7 @@ def host(t):
 
 GRAPHS = [(2, 1, False), (2, 1, True), (4, 1, False), (8, 3, True), (16, 2, False), (64, 64, False), (64, 100, True),
           (512, 4, False), (1024, 1, False), (2048, 100, True), (8192, 8, True), (65536, 4, True)] + \
-         [(4096, k, False) for k in (2, 4, 8, 16, 32)]
+         [(4096, k, False) for k in (2, 4, 8, 16, 32)] + [(262144, 2, False), (1048576, 1, True)]   # 25 M and 50 M edges
 
 
 @pytest.mark.parametrize("n,k,causal", GRAPHS)
@@ -174,6 +174,11 @@ FULL = ["cls", "lm", "xl", "ksweep2", "ksweep4", "ksweep8", "ksweep16", "ksweep3
 def test_full_size_configuration(name):
     # configurations 2-5 at their full sizes, every output element against the oracle
     run_case(WORKLOADS[name])
+
+
+def test_sequence_of_262144_tokens():
+    # four times the longest benchmark sequence, one (batch, head): 19 levels, every output element
+    run_case(Workload("long", 26, 262144, 2, True, 1, 1, 64, "bf16", True))
 
 
 def run_lengths_case(w: Workload, lengths, poison=50.0):
