@@ -48,6 +48,7 @@ struct TileArgs {
     const float* lse_r;
     float* dQ;
     float2 *stat, *wp;
+    bf16_t* dst;   // DENSE variant: dS^T of every block of 32 token rows, [batch*head][block][tile of the block][hi | lo][cid_pad][16 rows]
     // sequences shorter than n
     const int32_t *seq_len, *id_to_cid;
     int32_t n, k, W, ctx_levels, causal;
@@ -84,6 +85,17 @@ __device__ __forceinline__ bf16x8_t lds_transposed_b(const bf16_t* rows, int str
     const bf16_t* p = rows + (4 * g + (j >> 2)) * stride + 16 * f + 4 * (j & 3);
     const s16x4_t x = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)p);
     const s16x4_t y = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p + 16 * stride));
+    typedef short s16x8_t __attribute__((ext_vector_type(8)));
+    const s16x8_t xy = {x[0], x[1], x[2], x[3], y[0], y[1], y[2], y[3]};
+    return __builtin_bit_cast(bf16x8_t, xy);
+}
+
+// 8 consecutive k of the operand row/column `col0 + j`: two transposing reads of 4 rows each
+__device__ __forceinline__ bf16x8_t lds_tr8(const bf16_t* base, int stride, int row0, int col0, int j) {
+    typedef __attribute__((address_space(3))) s16x4_t* lds_ptr_t;
+    const bf16_t* p = base + (row0 + (j >> 2)) * stride + col0 + 4 * (j & 3);
+    const s16x4_t x = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)p);
+    const s16x4_t y = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p + 4 * stride));
     typedef short s16x8_t __attribute__((ext_vector_type(8)));
     const s16x8_t xy = {x[0], x[1], x[2], x[3], y[0], y[1], y[2], y[3]};
     return __builtin_bit_cast(bf16x8_t, xy);
@@ -398,8 +410,19 @@ __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArg
 // order for the d_rel kernel, which also adds the relative-position part of dQ.
 // REL_LDS: the compact relative-position table is staged in LDS; otherwise (large tables) its rows
 // are read from memory when a tile forms its bias table.
-template <bool REL_LDS, bool DROP>
+// DENSE (needs REL_LDS and cid_pad a multiple of 32): a tile's w = p dP and p are not stored per slot
+// for rel_grad_tile_kernel but scattered into two LDS tables [token][compact id] (the ids of a token
+// row are distinct).  When the tile is complete and delta is known, dS = w - delta p is there as a
+// dense 16 x cid_pad matrix: the relative-position part of dQ, scale * dS x Rel, is taken at once
+// (A operands from those tables, B operands by transposing reads of the staged table), and dS^T
+// leaves for rel_grad_dense_kernel already split into bf16 hi and lo and laid out as that kernel's A
+// operands -- 128 bytes per (block of 32 rows, id) instead of 8 bytes per tile slot, no scatter and no
+// second pass over dQ there.  (Layout per block: [tile][hi | lo][id][16 rows], so that the lanes of a
+// store, one id each, write adjacent 32-byte pieces; with the two tiles' rows of an id side by side a
+// store touched 64 lines and the stage cost 0.028 ms of 0.17.)
+template <bool REL_LDS, bool DROP, bool DENSE = false>
 __global__ void __launch_bounds__(kTileThreads, 2) bwd_q_tile_kernel(const TileArgs a) {
+    static_assert(!DENSE || REL_LDS, "the dense variant multiplies by the staged table");
     extern __shared__ __align__(16) unsigned char smem[];
     bf16_t* rel_s = reinterpret_cast<bf16_t*>(smem);
     const int lane = threadIdx.x & 63;
@@ -414,6 +437,9 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_q_tile_kernel(const TileA
     bf16_t* v_s = k_s + 32 * kRowStride;                                // the same for V rows
     int32_t* relid_s = reinterpret_cast<int32_t*>(smem + rel_bytes + (size_t)kTileWaves * 16 * a.bias_stride * sizeof(float) +
                                                   (size_t)kTileWaves * 64 * kRowStride * sizeof(bf16_t));   // [cid_pad], DROP
+    // DENSE: w and p of the tile, [16 tokens][bias_stride] each, after relid_s
+    float* w_s = reinterpret_cast<float*>(relid_s + a.cid_pad) + (size_t)wave * 32 * a.bias_stride;
+    float* p_s = w_s + 16 * a.bias_stride;
     if (DROP)
         for (int i = threadIdx.x; i < a.cid_pad; i += blockDim.x) relid_s[i] = i < a.num_cids ? a.cid_to_id[i] : 0;
     if (REL_LDS) {
@@ -555,6 +581,9 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_q_tile_kernel(const TileA
                 wave_lds_sync();
                 mask_bias(a, bias_s, cc.tile * 16, seq_length_u(a.seq_len, cc.bh / a.H, a.n), g, j);
             }
+            if (DENSE)   // w_s and p_s are adjacent; the previous tile's reads ended with a wave_lds_sync
+                for (int i = lane * 4; i < 32 * a.bias_stride; i += 256)
+                    *reinterpret_cast<f32x4_t*>(w_s + i) = f32x4_t{0.f, 0.f, 0.f, 0.f};
         }
         wave_lds_sync();  // the previous pair's reads of k_s, v_s (and the previous tile's of bias_s) are done
 #pragma unroll
@@ -616,10 +645,19 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_q_tile_kernel(const TileA
                 pw[c][r] = wgt;
                 pp[c][r] = p;
             }
-            // (w, p) of this lane's 4 columns: 32 contiguous bytes, a chunk is 2 KB contiguous
-            float4* dst = reinterpret_cast<float4*>(wp_t + ((int64_t)(cc.cp0 + 2 * cc.pair + c) * 16 + j) * 16 + 4 * g);
-            dst[0] = make_float4(pw[c][0], pp[c][0], pw[c][1], pp[c][1]);
-            dst[1] = make_float4(pw[c][2], pp[c][2], pw[c][3], pp[c][3]);
+            if (DENSE) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (cid[c][r] >= 0) {
+                        w_s[j * a.bias_stride + cid[c][r]] = pw[c][r];
+                        p_s[j * a.bias_stride + cid[c][r]] = pp[c][r];
+                    }
+            } else {
+                // (w, p) of this lane's 4 columns: 32 contiguous bytes, a chunk is 2 KB contiguous
+                float4* dst = reinterpret_cast<float4*>(wp_t + ((int64_t)(cc.cp0 + 2 * cc.pair + c) * 16 + j) * 16 + 4 * g);
+                dst[0] = make_float4(pw[c][0], pp[c][0], pw[c][1], pp[c][1]);
+                dst[1] = make_float4(pw[c][2], pp[c][2], pw[c][3], pp[c][3]);
+            }
         }
         // W and P as A operands, each split into bf16 hi + lo: A - delta*Bv cancels when a
         // row's softmax is peaked, so the two products need more than 8 mantissa bits
@@ -650,13 +688,63 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_q_tile_kernel(const TileA
             delta += __shfl_xor(delta, 32);
             const int len = seq_length_u(a.seq_len, cc.bh / a.H, a.n);
             if (g == 0) a.stat[(int64_t)cc.bh * a.N + t0 + j] = make_float2(t0 + j < len ? lse2 : kLseGone, delta);
+            f32x4_t dqr[4];
+#pragma unroll
+            for (int f = 0; f < 4; ++f) dqr[f] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            if (DENSE) {
+                wave_lds_sync();   // the scattered w and p of all lanes are in place
+                // dS as bf16 hi and lo, [16 tokens][cid_pad + 8], in the row buffers (free until the next pair is staged)
+                const int dstride = a.cid_pad + 8;
+                bf16_t* ds_h = k_s;
+                bf16_t* ds_l = k_s + 16 * dstride;
+                // relative-position part of dQ: dS [token j][ids] x Rel [ids][features]
+                for (int ks = 0; ks < a.cid_pad; ks += 32) {
+                    const f32x4_t w0 = *reinterpret_cast<const f32x4_t*>(w_s + j * a.bias_stride + ks + 8 * g);
+                    const f32x4_t w1 = *reinterpret_cast<const f32x4_t*>(w_s + j * a.bias_stride + ks + 8 * g + 4);
+                    const f32x4_t p0 = *reinterpret_cast<const f32x4_t*>(p_s + j * a.bias_stride + ks + 8 * g);
+                    const f32x4_t p1 = *reinterpret_cast<const f32x4_t*>(p_s + j * a.bias_stride + ks + 8 * g + 4);
+                    uint32_t hi[4], lo[4];
+                    split_pack(w0[0] - delta * p0[0], w0[1] - delta * p0[1], hi[0], lo[0]);
+                    split_pack(w0[2] - delta * p0[2], w0[3] - delta * p0[3], hi[1], lo[1]);
+                    split_pack(w1[0] - delta * p1[0], w1[1] - delta * p1[1], hi[2], lo[2]);
+                    split_pack(w1[2] - delta * p1[2], w1[3] - delta * p1[3], hi[3], lo[3]);
+                    const u32x4 xh = {hi[0], hi[1], hi[2], hi[3]}, xl = {lo[0], lo[1], lo[2], lo[3]};
+                    const bf16x8_t aH = __builtin_bit_cast(bf16x8_t, xh), aL = __builtin_bit_cast(bf16x8_t, xl);
+                    *reinterpret_cast<u32x4*>(ds_h + j * dstride + ks + 8 * g) = xh;
+                    *reinterpret_cast<u32x4*>(ds_l + j * dstride + ks + 8 * g) = xl;
+#pragma unroll
+                    for (int f = 0; f < 4; ++f) {
+                        const bf16x8_t rB = lds_tr8(rel_s, kRelStride, ks + 8 * g, 16 * f, j);
+                        dqr[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aH, rB, dqr[f], 0, 0, 0);
+                        dqr[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aL, rB, dqr[f], 0, 0, 0);
+                    }
+                }
+                // dS^T for the d_rel kernel: lane <-> compact id, the tile's 16 rows as bf16 hi and lo (32 bytes
+                // each), through the transposing LDS reads; consecutive lanes write consecutive 32-byte
+                // pieces: [tile of the block][hi | lo][id][16 rows]
+                wave_lds_sync();
+                bf16_t* blk_out = a.dst + (((int64_t)cc.bh * ((a.num_tiles + 1) >> 1) + (cc.tile >> 1)) * 4 + 2 * (cc.tile & 1)) *
+                                              a.cid_pad * 16;
+                for (int c0 = 0; c0 < a.cid_pad; c0 += 64) {
+                    const int c = c0 + lane;
+                    if (c < a.cid_pad) {
+                        uint4* oh = reinterpret_cast<uint4*>(blk_out + c * 16);
+                        uint4* ol = reinterpret_cast<uint4*>(blk_out + (a.cid_pad + c) * 16);
+                        oh[0] = __builtin_bit_cast(uint4, lds_tr8(ds_h, dstride, 0, c0 + 16 * g, j));
+                        oh[1] = __builtin_bit_cast(uint4, lds_tr8(ds_h, dstride, 8, c0 + 16 * g, j));
+                        ol[0] = __builtin_bit_cast(uint4, lds_tr8(ds_l, dstride, 0, c0 + 16 * g, j));
+                        ol[1] = __builtin_bit_cast(uint4, lds_tr8(ds_l, dstride, 8, c0 + 16 * g, j));
+                    }
+                }
+                wave_lds_sync();   // before the next tile clears the tables
+            }
             float* qrow_out = a.dQ + base + (int64_t)t0 * a.sn + j;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const float dr = __shfl(delta, 4 * g + r);
 #pragma unroll
                 for (int f = 0; f < 4; ++f)
-                    qrow_out[(int64_t)(4 * g + r) * a.sn + 16 * f] = a.scale * (ow[f][r] - dr * op[f][r]);
+                    qrow_out[(int64_t)(4 * g + r) * a.sn + 16 * f] = a.scale * (ow[f][r] - dr * op[f][r] + dqr[f][r]);
             }
         }
         cc = cr;
@@ -688,17 +776,6 @@ struct RelGradArgs {
     float scale;
     const int32_t* seq_len;   // [B] tokens of every sequence, or null
 };
-// 8 consecutive k of the operand row/column `col0 + j`: two transposing reads of 4 rows each
-__device__ __forceinline__ bf16x8_t lds_tr8(const bf16_t* base, int stride, int row0, int col0, int j) {
-    typedef __attribute__((address_space(3))) s16x4_t* lds_ptr_t;
-    const bf16_t* p = base + (row0 + (j >> 2)) * stride + col0 + 4 * (j & 3);
-    const s16x4_t x = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)p);
-    const s16x4_t y = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p + 4 * stride));
-    typedef short s16x8_t __attribute__((ext_vector_type(8)));
-    const s16x8_t xy = {x[0], x[1], x[2], x[3], y[0], y[1], y[2], y[3]};
-    return __builtin_bit_cast(bf16x8_t, xy);
-}
-
 // tile slots per thread fetched one block ahead: 8 (512 threads: 16 chunks) with up to 256 ids, 24 with more --
 // those graphs have 25..30 slots per thread and block, and one workgroup per compute unit to hide their latency
 template <int CPW>
@@ -871,6 +948,112 @@ __global__ void __launch_bounds__(kThreads, CPW == 2 ? 4 : 2) rel_grad_tile_kern
             for (int f = 0; f < 4; ++f)
 #pragma unroll
                 for (int m = 0; m < 4; ++m) dst[(16 * chunk + 4 * g + m) * kD + 16 * f + j] = acc[c][f][m] * a.scale;
+        }
+    }
+}
+
+// d_rel from the dense dS^T blocks of bwd_q_tile_kernel<.., DENSE>: per block of 32 token rows
+//   d_rel[id][f] += dS^T (A: hi and lo, read from memory in operand layout) x Q (B: the block's rows,
+//   staged in LDS, transposing reads).
+// Wavefront w owns the id chunks w, w + 8, ...; its accumulators live across the blocks the workgroup
+// walks and are written once, as this workgroup's copy, in compact-id order (summed by
+// drel_reduce_kernel in a fixed order).  The operands of the next block are requested while the
+// current one is multiplied.  A token tile past the end of a shorter sequence was not computed: its
+// half of the block counts as zero.
+template <int CPW>
+__global__ void __launch_bounds__(kThreads) rel_grad_dense_kernel(const RelGradArgs a, const bf16_t* __restrict__ dst) {
+    __shared__ __align__(16) bf16_t q_s[2][kRgRows * kRowStride];   // the block's Q rows, two buffers used alternately
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int g = lane >> 4, j = lane & 15;
+    const int nids = a.nids, nchunks = nids >> 4;
+    const int blocks_per_bh = (a.num_tiles + 1) >> 1;
+    const int total = a.BH * blocks_per_bh;
+
+    f32x4_t acc[CPW][4];
+#pragma unroll
+    for (int c = 0; c < CPW; ++c)
+#pragma unroll
+        for (int f = 0; f < 4; ++f) acc[c][f] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    uint4 qpiece = make_uint4(0u, 0u, 0u, 0u);
+    uint4 ah[CPW], al[CPW];
+    auto prefetch = [&](int blk) {
+        const int bh = blk / blocks_per_bh, b = walk_pos(a.seq_len, bh, blk - bh * blocks_per_bh, blocks_per_bh), row0 = kRgRows * b;
+        const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
+        const int len = seq_length_u(a.seq_len, bh / a.H, a.n);
+        qpiece = make_uint4(0u, 0u, 0u, 0u);
+        if (threadIdx.x < kRgRows * 8) {
+            const int r = threadIdx.x >> 3, c = (threadIdx.x & 7) * 8;
+            if (row0 + r < a.n) qpiece = *reinterpret_cast<const uint4*>(a.Q + base + (int64_t)(row0 + r) * a.sn + c);
+        }
+        // this lane's rows 8g..8g+7 lie in the first (g < 2) or the second tile of the block
+        const bool live = row0 + 16 * (g >> 1) < len;
+        // [tile of the block][hi | lo][id][16 rows]
+        const bf16_t* src = dst + (((int64_t)bh * blocks_per_bh + b) * 4 + 2 * (g >> 1)) * nids * 16 + 8 * (g & 1);
+#pragma unroll
+        for (int c = 0; c < CPW; ++c) {
+            const int chunk = wave + kWaves * c;
+            ah[c] = al[c] = make_uint4(0u, 0u, 0u, 0u);
+            if (chunk < nchunks && live) {
+                const bf16_t* p = src + (16 * chunk + j) * 16;
+                ah[c] = *reinterpret_cast<const uint4*>(p);
+                al[c] = *reinterpret_cast<const uint4*>(p + nids * 16);
+            }
+        }
+    };
+    // blocks past the end of a shorter sequence add nothing and are stepped over (uniform for the workgroup)
+    auto next_block = [&](int blk) {
+        if (a.seq_len)
+            for (; blk < total; blk += gridDim.x) {
+                const int bh = blk / blocks_per_bh;
+                if (walk_pos(a.seq_len, bh, blk - bh * blocks_per_bh, blocks_per_bh) * kRgRows < seq_length_u(a.seq_len, bh / a.H, a.n)) break;
+            }
+        return blk;
+    };
+    int blk = next_block(blockIdx.x);
+    if (blk < total) prefetch(blk);
+    int buf = 0;
+    while (blk < total) {
+        bf16_t* q_b = q_s[buf];
+        if (threadIdx.x < kRgRows * 8)
+            *reinterpret_cast<uint4*>(q_b + (threadIdx.x >> 3) * kRowStride + (threadIdx.x & 7) * 8) = qpiece;
+        uint4 ch[CPW], cl[CPW];
+#pragma unroll
+        for (int c = 0; c < CPW; ++c) {
+            ch[c] = ah[c];
+            cl[c] = al[c];
+        }
+        const int blk_next = next_block(blk + gridDim.x);
+        if (blk_next < total) prefetch(blk_next);
+        __syncthreads();   // the rows are staged; the buffer written next was last read two blocks ago
+        bf16x8_t qb[4];
+#pragma unroll
+        for (int f = 0; f < 4; ++f) qb[f] = lds_tr8(q_b, kRowStride, 8 * g, 16 * f, j);
+#pragma unroll
+        for (int c = 0; c < CPW; ++c) {
+            if (wave + kWaves * c < nchunks) {
+                const bf16x8_t xh = __builtin_bit_cast(bf16x8_t, ch[c]), xl = __builtin_bit_cast(bf16x8_t, cl[c]);
+#pragma unroll
+                for (int f = 0; f < 4; ++f) {
+                    acc[c][f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xh, qb[f], acc[c][f], 0, 0, 0);
+                    acc[c][f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xl, qb[f], acc[c][f], 0, 0, 0);
+                }
+            }
+        }
+        buf ^= 1;
+        blk = blk_next;
+    }
+    // this workgroup's copy: [gridDim.x][nids][kD], compact-id order
+    float* out = a.drel_part + (int64_t)blockIdx.x * nids * kD;
+#pragma unroll
+    for (int c = 0; c < CPW; ++c) {
+        const int chunk = wave + kWaves * c;
+        if (chunk < nchunks) {
+#pragma unroll
+            for (int f = 0; f < 4; ++f)
+#pragma unroll
+                for (int m = 0; m < 4; ++m) out[(16 * chunk + 4 * g + m) * kD + 16 * f + j] = acc[c][f][m] * a.scale;
         }
     }
 }

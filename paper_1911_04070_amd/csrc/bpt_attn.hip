@@ -144,18 +144,22 @@ struct TilePlan {
     int cid_pad = 0, bias_stride = 0;
     size_t lds = 0;
 };
-TilePlan plan_tiles(const bpt_graph* g, const DeviceLimits& lim) {
+// dense: the plan of bwd_q_tile_kernel<.., DENSE> -- ids padded to 32, two more [16][bias_stride] fp32
+// tables per wavefront, and the relative-position table must be in LDS
+TilePlan plan_tiles(const bpt_graph* g, const DeviceLimits& lim, bool dense = false) {
     TilePlan t;
     if (g->tiles.num_tiles == 0) return t;
-    t.cid_pad = (g->tiles.num_cids + 15) & ~15;
+    t.cid_pad = dense ? (g->tiles.num_cids + 31) & ~31 : (g->tiles.num_cids + 15) & ~15;
     t.bias_stride = t.cid_pad + ((4 - t.cid_pad % 32) + 32) % 32;  // = 4 mod 32: the 16 token rows hit different banks
     const size_t rel = (size_t)t.cid_pad * kRelStride * sizeof(bf16_t);
     const size_t rest = (size_t)kTileWaves * 16 * t.bias_stride * sizeof(float) +
                         (size_t)kTileWaves * 64 * kRowStride * sizeof(bf16_t) +
-                        (size_t)t.cid_pad * sizeof(int32_t);   // relative-position ids of the compact ids (dropout)
+                        (size_t)t.cid_pad * sizeof(int32_t) +   // relative-position ids of the compact ids (dropout)
+                        (dense ? (size_t)kTileWaves * 32 * t.bias_stride * sizeof(float) : 0);
     t.rel_lds = rel + rest <= lim.lds;
     t.lds = t.rel_lds ? rel + rest : rest;
-    t.ok = t.lds <= lim.lds;
+    // (dense: dS of a tile, bf16 hi and lo with 16 bytes of padding per row, has to fit a wavefront's row buffers)
+    t.ok = dense ? t.rel_lds && 64 * (t.cid_pad + 8) <= 64 * kRowStride * (int)sizeof(bf16_t) : t.lds <= lim.lds;
     return t;
 }
 
@@ -173,10 +177,15 @@ int launch_tiles(const char* name, K kernel, const TileArgs& t, const DeviceLimi
 }
 
 // bf16 backward, query side of the token rows on dense tiles
-int run_bwd_q_tiles(const bpt_graph* g, const AttnArgs& a, const DeviceLimits& lim, hipStream_t st) {
-    const TilePlan tp = plan_tiles(g, lim);
+int run_bwd_q_tiles(const bpt_graph* g, const AttnArgs& a, const DeviceLimits& lim, bool dense, hipStream_t st) {
+    const TilePlan tp = plan_tiles(g, lim, dense);
     TileArgs t = {};
     fill_tile_args(t, g, a, tp);
+    if (dense) {   // dS^T blocks take the place of the (w, p) pairs in the workspace
+        t.dst = reinterpret_cast<bf16_t*>(a.wp);
+        return a.drop_thr ? launch_tiles("bwd_q_tile_kernel", bwd_q_tile_kernel<true, true, true>, t, lim, tp.lds, st)
+                          : launch_tiles("bwd_q_tile_kernel", bwd_q_tile_kernel<true, false, true>, t, lim, tp.lds, st);
+    }
     if (a.drop_thr)
         return tp.rel_lds ? launch_tiles("bwd_q_tile_kernel", bwd_q_tile_kernel<true, true>, t, lim, tp.lds, st)
                           : launch_tiles("bwd_q_tile_kernel", bwd_q_tile_kernel<false, true>, t, lim, tp.lds, st);
@@ -358,6 +367,7 @@ struct BwdPlan {
     bool drel_tile = false;   // bf16 tensors with token tiles and at most 256 ids in use: rel_grad_tile_kernel
     int drel_part_rows = 0;   // rows of one workgroup's copy of d_rel
     bool q_tiles = false;     // query side of token rows on dense tiles (bwd_q_tile_kernel)
+    bool dense_ds = false;    // ... which hands dS^T blocks (not (w, p) pairs) to rel_grad_dense_kernel
     bool kv_tiles = false;    // key side on dense tiles of key nodes (bwd_kv_tile_kernel)
     size_t kv_lds = 0;
     int drel_ipw = 32;        // ids per wavefront: 8, 16 or 32
@@ -385,6 +395,10 @@ int plan_bwd(const bpt_graph* g, const bpt_shape_t* s, BwdPlan* p) {
             p->drel_tile = true;
             p->drel_part_rows = cids;
             p->drel_lds = rg_lds;
+            if (cids <= 16 * kWaves * 2 && plan_tiles(g, lim, true).ok) {
+                p->dense_ds = true;
+                p->drel_lds = 2 * kRgRows * kRowStride * sizeof(bf16_t);   // static, for the occupancy estimate below
+            }
         }
         if (g->ktiles.num_tasks > 0 && g->ktiles.nb_pad <= 16 * kMaxBiasChunks) {
             const int parked = std::max(0, g->ktiles.nb_pad / 16 - kRegBiasChunks);   // table operands kept in LDS
@@ -410,7 +424,9 @@ int plan_bwd(const bpt_graph* g, const bpt_shape_t* s, BwdPlan* p) {
     off += align_up(bh * g->num_nodes * sizeof(float2));
     p->off_wp = off;
     // (w, p) pairs: per edge of a token row in CSR order, or per slot of the token tiles
-    off += align_up(bh * (p->q_tiles ? (size_t)g->tiles.num_chunks * 256 : (size_t)g->num_token_edges) * sizeof(float2));
+    // or, with dense_ds, 128 bytes per (block of 32 token rows, compact id)
+    off += align_up(p->dense_ds ? bh * (size_t)((g->tiles.num_tiles + 1) / 2) * p->drel_part_rows * 128
+                                : bh * (p->q_tiles ? (size_t)g->tiles.num_chunks * 256 : (size_t)g->num_token_edges) * sizeof(float2));
     p->off_qpart = off;
     off += align_up(bh * std::max<size_t>(std::max(g->fwd.num_part, g->fwd_span.num_part), span_partials(g)) *
                     kQPartStride * sizeof(float));
@@ -455,7 +471,7 @@ int run_bwd_q(const bpt_graph* g, const BwdPlan& p, AttnArgs& a, hipStream_t st)
     a.drel_block = p.drel_block;
     const Schedule* sc = &g->fwd;
     if (p.q_tiles) {  // token rows on the matrix cores; the gather kernel below only sees span rows
-        if ((rc = run_bwd_q_tiles(g, a, lim, st))) return rc;
+        if ((rc = run_bwd_q_tiles(g, a, lim, p.dense_ds, st))) return rc;
         use_schedule(a, g->fwd_span);
         sc = &g->fwd_span;
     }
@@ -501,7 +517,10 @@ int run_bwd_q(const bpt_graph* g, const BwdPlan& p, AttnArgs& a, hipStream_t st)
         t.nids = p.drel_part_rows;
         t.scale = a.scale;
         t.seq_len = a.seq_len;
-        if (p.drel_part_rows <= 256) {
+        if (p.dense_ds) {
+            BPT_LAUNCH("rel_grad_dense_kernel", rel_grad_dense_kernel<2>, dim3(p.drel_grid_x), dim3(kThreads), 0, st, t,
+                       reinterpret_cast<const bf16_t*>(a.wp));
+        } else if (p.drel_part_rows <= 256) {
             if (p.drel_lds > 65536)
                 BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rel_grad_tile_kernel<2>),
                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.drel_lds));
