@@ -27,16 +27,16 @@ HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
 # workload; the runs and their commands are in profiles/.  None where not measured.
 MEASURED_TRAFFIC = {
     "lm": {  # profiles/lm_n8192_k8_causal_bf16_kernels.md
-        "bwd_kv_tile_kernel": int((223979.5 * 2.0 + 279937.0) * 1024),
-        "bwd_q_tile_kernel": int((144196.4 * 2.0 + 309269.9) * 1024),
-        "rel_grad_tile_kernel": int((173082.0 * 2.0 + 90112.3) * 1024),
-        "fwd_tile_kernel": int((117065.4 * 2.0 + 33873.9) * 1024),
-        "bwd_q_span_tile_kernel": int((67578.0 * 2.0 + 99726.8) * 1024),
-        "fwd_span_tile_kernel": int((49578.9 * 2.0 + 49978.8) * 1024),
+        "bwd_kv_tile_kernel": int((223688.0 * 2.0 + 279937.0) * 1024),
+        "bwd_q_tile_kernel": int((133085.0 * 2.0 + 165975.0) * 1024),
+        "rel_grad_dense_kernel": int((65576.0 * 2.0 + 24576.0) * 1024),
+        "fwd_tile_kernel": int((117165.0 * 2.0 + 33874.0) * 1024),
+        "bwd_q_span_tile_kernel": int((67578.0 * 2.0 + 99730.0) * 1024),
+        "fwd_span_tile_kernel": int((49577.0 * 2.0 + 49977.0) * 1024),
     },
 }
 # HBM bytes of one whole step (all kernels, same counters and scaling)
-MEASURED_STEP_TRAFFIC = {"lm": 2584055600}
+MEASURED_STEP_TRAFFIC = {"lm": 2126708768}
 
 
 def parse():

@@ -38,10 +38,12 @@ struct KeyArgs {
     int32_t n;
     uint32_t drop_thr, drop_seed;   // dropout on the attention weights (DROP variants)
     float drop_inv_keep;
-    int32_t* queue;   // 8 task counters (one per XCD, 64 bytes apart), zero when the kernel starts
+    // 8 task counters (one per XCD, 64 bytes apart), zero when the kernel starts: cleared by the last kernel
+    // of the query side when both sides run in one call, else by zero_ints_kernel
+    int32_t* queue;
 };
 
-// `count` ints = 0 (the task counters of bwd_kv_tile_kernel; a fill kernel, so that the call can be captured in a graph)
+// `count` ints = 0 (a fill kernel, so that the call can be captured in a graph)
 __global__ void zero_ints_kernel(int32_t* p, int count) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < count) p[i] = 0;
@@ -417,10 +419,14 @@ __global__ void __launch_bounds__(256) bwd_kv_merge_kernel(const AttnArgs a, con
 // independent partial sums in flight), then combine in a fixed tree.
 // With `id_to_cid` the copies are in the token tiles' compact-id order and hold
 // `covered_rows` rows each: row `id` of d_rel is copy row id_to_cid[id] (or zero).
+// The first workgroup also clears the `zero_count` ints at `zero`: the task counters of the key side,
+// which runs after the query side that ends with this kernel.
 __global__ void __launch_bounds__(1024) drel_reduce_kernel(const float* __restrict__ parts, int num_parts,
                                                            int covered_rows, const int32_t* __restrict__ id_to_cid,
-                                                           float* __restrict__ d_rel) {
+                                                           float* __restrict__ d_rel, int32_t* __restrict__ zero,
+                                                           int zero_count) {
     __shared__ float s[16][kD];
+    if (blockIdx.x == 0 && (int)threadIdx.x < zero_count) zero[threadIdx.x] = 0;
     const int row = blockIdx.x, lane = threadIdx.x & 63, grp = threadIdx.x >> 6;
     const int prow = id_to_cid ? id_to_cid[row] : row;
     float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f, a4 = 0.f, a5 = 0.f, a6 = 0.f, a7 = 0.f;

@@ -547,7 +547,7 @@ int run_bwd_q(const bpt_graph* g, const BwdPlan& p, AttnArgs& a, hipStream_t st)
     }
     if (rc) return rc;
     BPT_LAUNCH("drel_reduce_kernel", drel_reduce_kernel, dim3(a.rel_rows), dim3(1024), 0, st, a.drel_part, p.drel_grid_x,
-               p.drel_part_rows, p.drel_tile ? g->tiles.id_to_cid : nullptr, a.d_rel);
+               p.drel_part_rows, p.drel_tile ? g->tiles.id_to_cid : nullptr, a.d_rel, a.queue, kQueueInts);
     BPT_HIP(hipGetLastError());
     return BPT_OK;
 }
@@ -569,7 +569,9 @@ int launch_kv_tiles(const KeyArgs& t, const BwdPlan& p, const DeviceLimits& lim,
 }
 
 // bf16 key side on dense tiles of key nodes
-int run_bwd_kv_tiles(const bpt_graph* g, const BwdPlan& p, const AttnArgs& a, const DeviceLimits& lim, hipStream_t st) {
+// queue_cleared: the query side ran in the same call and its last kernel has put the task counters to zero
+int run_bwd_kv_tiles(const bpt_graph* g, const BwdPlan& p, const AttnArgs& a, const DeviceLimits& lim, bool queue_cleared,
+                     hipStream_t st) {
     const KeyTiles& kt = g->ktiles;
     KeyArgs t = {};
     t.Q = static_cast<const bf16_t*>(a.Q);
@@ -612,8 +614,10 @@ int run_bwd_kv_tiles(const bpt_graph* g, const BwdPlan& p, const AttnArgs& a, co
     t.drop_inv_keep = a.drop_inv_keep;
     t.queue = a.queue;
     if ((int64_t)a.BH * kt.num_tasks > INT32_MAX) return BPT_ERR_UNSUPPORTED;
-    BPT_LAUNCH("zero_ints_kernel", zero_ints_kernel, dim3(1), dim3(kQueueInts), 0, st, t.queue, kQueueInts);
-    BPT_HIP(hipGetLastError());
+    if (!queue_cleared) {
+        BPT_LAUNCH("zero_ints_kernel", zero_ints_kernel, dim3(1), dim3(kQueueInts), 0, st, t.queue, kQueueInts);
+        BPT_HIP(hipGetLastError());
+    }
     int rc = BPT_ERR_UNSUPPORTED;
     switch (kt.nb_pad / 16) {
         case 1: rc = launch_kv_tiles<1>(t, p, lim, st); break;
@@ -641,11 +645,11 @@ int run_bwd_kv_tiles(const bpt_graph* g, const BwdPlan& p, const AttnArgs& a, co
 }
 
 template <typename T>
-int run_bwd_kv(const bpt_graph* g, const BwdPlan& p, AttnArgs& a, hipStream_t st) {
+int run_bwd_kv(const bpt_graph* g, const BwdPlan& p, AttnArgs& a, bool queue_cleared, hipStream_t st) {
     DeviceLimits lim;
     int rc = device_limits(g, &lim);
     if (rc) return rc;
-    if (p.kv_tiles) return run_bwd_kv_tiles(g, p, a, lim, st);
+    if (p.kv_tiles) return run_bwd_kv_tiles(g, p, a, lim, queue_cleared, st);
     a.ptr = g->t_ptr;
     a.ia = g->t_src;
     a.ib = g->t_rel;
@@ -714,7 +718,8 @@ int backward(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q, const vo
     }
     if (stages & kStageKV) {
         a.part = reinterpret_cast<float*>(ws + p.off_kvpart);
-        if ((rc = bf ? run_bwd_kv<bf16_t>(g, p, a, st) : run_bwd_kv<float>(g, p, a, st))) return rc;
+        const bool cleared = (stages & kStageQ) != 0;
+        if ((rc = bf ? run_bwd_kv<bf16_t>(g, p, a, cleared, st) : run_bwd_kv<float>(g, p, a, cleared, st))) return rc;
     }
     return BPT_OK;
 }
