@@ -416,7 +416,9 @@ int plan_bwd(const bpt_graph* g, const bpt_shape_t* s, BwdPlan* p) {
         p->drel_grid_y = (p->drel_rows + chunk - 1) / chunk;
         blocks = (int64_t)s->B * s->H * (g->n / p->drel_block);
     }
-    const int per_cu = (int)std::max<size_t>(1, std::min<size_t>(4, lim.lds_cu / p->drel_lds));
+    // workgroups per compute unit (every workgroup writes its own copy of d_rel: no more of them than run at once;
+    // the dense kernel's registers allow two)
+    const int per_cu = p->dense_ds ? 2 : (int)std::max<size_t>(1, std::min<size_t>(4, lim.lds_cu / p->drel_lds));
     p->drel_grid_x = (int)std::max<int64_t>(1, std::min<int64_t>(blocks, (int64_t)lim.cus * per_cu / p->drel_grid_y));
     const size_t bh = (size_t)s->B * s->H;
     size_t off = 0;
