@@ -23,7 +23,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
-# HBM bytes per launch of a kernel, from rocprofv3 FETCH_SIZE (x2.0) + WRITE_SIZE on this
+# HBM bytes per launch of a kernel, from rocprofv3 FETCH_SIZE (x2.0: the counter reads half the bytes of a
+# plain device copy of known size, `--calibrate-copy-mib`) + WRITE_SIZE on this
 # workload; the runs and their commands are in profiles/.  None where not measured.
 MEASURED_TRAFFIC = {
     "lm": {  # profiles/lm_n8192_k8_causal_bf16_kernels.md
@@ -127,7 +128,7 @@ def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (--gpus 1); the path shards over (batch, head) "
-              "without communication, see DESIGN.md", file=sys.stderr)
+              "without communication (one all-reduce of d_rel in the backward)", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
@@ -239,7 +240,7 @@ def main():
     copy_gbs = 2.0 * src.numel() / (copy_ms * 1e-3) / 1e9
     del src, dst
 
-    # algorithmic bytes per launch (DESIGN.md section 6): every edge-instance a gather kernel handles counts one
+    # algorithmic bytes per launch: every edge-instance a gather kernel handles counts one
     # key row + one value row (or one query row + one dout row): 256 B in bf16, 512 B in fp32
     bh = w.B * w.H
     if lengths is None:
