@@ -9,7 +9,6 @@
 #include <rocblas/rocblas.h>
 
 #include <algorithm>
-#include <mutex>
 
 #include "bpt_internal.h"
 
@@ -359,11 +358,10 @@ __global__ void __launch_bounds__(256) add_cast_kernel(const bf16_t* __restrict_
     *reinterpret_cast<uint4*>(y + i * 8) = make_uint4(o[0], o[1], o[2], o[3]);
 }
 
-// one rocBLAS handle per device, created on first use
+// one rocBLAS handle per host thread and device, created on first use and kept: a handle carries the
+// stream of the call in progress, so two host threads must not share one
 rocblas_handle blas_handle(int device) {
-    static std::mutex mu;
-    static rocblas_handle handles[64] = {};
-    std::lock_guard<std::mutex> lock(mu);
+    thread_local rocblas_handle handles[64] = {};
     if (device < 0 || device >= 64) return nullptr;
     if (!handles[device] && rocblas_create_handle(&handles[device]) != rocblas_status_success) handles[device] = nullptr;
     return handles[device];
