@@ -31,6 +31,7 @@ constexpr int kRelStride = 72;   // bf16 per LDS row of the compact table (64 + 
 constexpr int kVStride = 68;     // bf16 per LDS row of a staged V row (136 B)
 constexpr int kRowStride = 72;   // bf16 per LDS row where rows are written and read 16 bytes at a time (144 B)
 
+constexpr int kDenseChunks = 8;   // 16-id chunks the dense variant of bwd_q_tile_kernel keeps d_rel sums for
 struct TileArgs {
     const bf16_t *Q, *K, *V, *rel;
     bf16_t* out;
@@ -48,7 +49,7 @@ struct TileArgs {
     const float* lse_r;
     float* dQ;
     float2 *stat, *wp;
-    bf16_t* dst;   // DENSE variant: dS^T of every block of 32 token rows, [batch*head][block][tile of the block][hi | lo][cid_pad][16 rows]
+    float* drel_part;   // DENSE variant: the workgroups' copies of d_rel, [workgroup][cid_pad][64]
     // sequences shorter than n
     const int32_t *seq_len, *id_to_cid;
     int32_t n, k, W, ctx_levels, causal;
@@ -99,6 +100,13 @@ __device__ __forceinline__ bf16x8_t lds_tr8(const bf16_t* base, int stride, int 
     typedef short s16x8_t __attribute__((ext_vector_type(8)));
     const s16x8_t xy = {x[0], x[1], x[2], x[3], y[0], y[1], y[2], y[3]};
     return __builtin_bit_cast(bf16x8_t, xy);
+}
+
+// 4 consecutive k (rows row0 .. row0 + 3) of the operand column `col0 + j`: one transposing read, the
+// operand of v_mfma_f32_16x16x16_bf16 for k = 4g .. 4g + 3
+__device__ __forceinline__ s16x4_t lds_tr4(const bf16_t* base, int stride, int row0, int col0, int j) {
+    typedef __attribute__((address_space(3))) s16x4_t* lds_ptr_t;
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(base + (row0 + (j >> 2)) * stride + col0 + 4 * (j & 3)));
 }
 
 // Sequences shorter than n: the bias entries of edges such a sequence does not have are set to
@@ -413,15 +421,14 @@ __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArg
 // DENSE (needs REL_LDS and cid_pad a multiple of 32): a tile's w = p dP and p are not stored per slot
 // for rel_grad_tile_kernel but scattered into two LDS tables [token][compact id] (the ids of a token
 // row are distinct).  When the tile is complete and delta is known, dS = w - delta p is there as a
-// dense 16 x cid_pad matrix: the relative-position part of dQ, scale * dS x Rel, is taken at once
-// (A operands from those tables, B operands by transposing reads of the staged table), and dS^T
-// leaves for rel_grad_dense_kernel already split into bf16 hi and lo and laid out as that kernel's A
-// operands -- 128 bytes per (block of 32 rows, id) instead of 8 bytes per tile slot, no scatter and no
-// second pass over dQ there.  (Layout per block: [tile][hi | lo][id][16 rows], so that the lanes of a
-// store, one id each, write adjacent 32-byte pieces; with the two tiles' rows of an id side by side a
-// store touched 64 lines and the stage cost 0.028 ms of 0.17.)
+// dense 16 x cid_pad matrix (kept as bf16 hi + lo in the row buffers): the relative-position part of
+// dQ, scale * dS x Rel, is taken at once (A operands from those tables, B operands by transposing
+// reads of the staged table), and so is the tile's share of d_rel, dS^T x Q, with both operands from
+// transposing reads, into accumulators the wavefront keeps over all its tiles (at most kDenseChunks
+// chunks of 16 ids).  Nothing per slot or per tile leaves for a d_rel kernel; every workgroup writes
+// one copy of d_rel at the end, and drel_reduce_kernel adds the copies in a fixed order.
 template <bool REL_LDS, bool DROP, bool DENSE = false>
-__global__ void __launch_bounds__(kTileThreads, 2) bwd_q_tile_kernel(const TileArgs a) {
+__global__ void __launch_bounds__(kTileThreads, DENSE ? 1 : 2) bwd_q_tile_kernel(const TileArgs a) {
     static_assert(!DENSE || REL_LDS, "the dense variant multiplies by the staged table");
     extern __shared__ __align__(16) unsigned char smem[];
     bf16_t* rel_s = reinterpret_cast<bf16_t*>(smem);
@@ -532,10 +539,49 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_q_tile_kernel(const TileA
         }
     };
 
+    // DENSE: this wavefront's d_rel sums over its tiles, [id chunk][feature chunk] in the C layout (id 4g + r
+    // of the chunk, feature 16f + j); written once, as this wavefront's copy, in compact-id order
+    f32x4_t racc[DENSE ? kDenseChunks : 1][4];
+#pragma unroll
+    for (int c = 0; c < (DENSE ? kDenseChunks : 1); ++c)
+#pragma unroll
+        for (int f = 0; f < 4; ++f) racc[c][f] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    // the four wavefronts' sums are added in wavefront order through LDS (all of it is free by then: every
+    // wavefront of the workgroup comes here exactly once, at its end) and leave as the workgroup's copy
+    auto write_drel = [&]() {
+        if (!DENSE) return;
+        __syncthreads();   // no wavefront of the workgroup still uses its tables
+        float* sum_s = reinterpret_cast<float*>(smem);   // [4 wavefronts][cid_pad][64]
+#pragma unroll
+        for (int c = 0; c < (DENSE ? kDenseChunks : 1); ++c)
+            if (16 * c < a.cid_pad) {
+#pragma unroll
+                for (int f = 0; f < 4; ++f)
+#pragma unroll
+                    for (int m = 0; m < 4; ++m)
+                        sum_s[((size_t)wave * a.cid_pad + 16 * c + 4 * g + m) * kD + 16 * f + j] = racc[c][f][m];
+            }
+        __syncthreads();
+        float* out = a.drel_part + (int64_t)blockIdx.x * a.cid_pad * kD;
+        const int count = a.cid_pad * kD;
+        for (int i = threadIdx.x * 4; i < count; i += kTileThreads * 4) {
+            f32x4_t t = *reinterpret_cast<const f32x4_t*>(sum_s + i);
+#pragma unroll
+            for (int w2 = 1; w2 < kTileWaves; ++w2) {
+                const f32x4_t x = *reinterpret_cast<const f32x4_t*>(sum_s + (size_t)w2 * count + i);
+                t[0] += x[0]; t[1] += x[1]; t[2] += x[2]; t[3] += x[3];
+            }
+            *reinterpret_cast<f32x4_t*>(out + i) = f32x4_t{t[0] * a.scale, t[1] * a.scale, t[2] * a.scale, t[3] * a.scale};
+        }
+    };
+
     TileCursor cc, cr, ci;
     cc.t = w.t;
     enter_tile(cc);
-    if (!cc.valid) return;
+    if (!cc.valid) {
+        write_drel();
+        return;
+    }
     load_idx(cc);
     request_rows(cc);
     uint2 mp[2] = {mp_n[0], mp_n[1]};
@@ -719,24 +765,27 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_q_tile_kernel(const TileA
                         dqr[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aL, rB, dqr[f], 0, 0, 0);
                     }
                 }
-                // dS^T for the d_rel kernel: lane <-> compact id, the tile's 16 rows as bf16 hi and lo (32 bytes
-                // each), through the transposing LDS reads; consecutive lanes write consecutive 32-byte
-                // pieces: [tile of the block][hi | lo][id][16 rows]
+                // d_rel += dS^T [ids][16 tokens] x Q [16 tokens][features], 16 ids at a time: the A operand is one
+                // transposing read of dS (tokens 4g .. 4g + 3 of id 16c + j), the B operand one of the tile's Q
+                // rows, put row-major where the bias table was (dead once the tile is complete)
+                bf16_t* q_t = reinterpret_cast<bf16_t*>(bias_s);   // [16 tokens][kRowStride]
+                *reinterpret_cast<bf16x8_t*>(q_t + j * kRowStride + 16 * g) = qb0;
+                *reinterpret_cast<bf16x8_t*>(q_t + j * kRowStride + 16 * g + 8) = qb1;
                 wave_lds_sync();
-                bf16_t* blk_out = a.dst + (((int64_t)cc.bh * ((a.num_tiles + 1) >> 1) + (cc.tile >> 1)) * 4 + 2 * (cc.tile & 1)) *
-                                              a.cid_pad * 16;
-                for (int c0 = 0; c0 < a.cid_pad; c0 += 64) {
-                    const int c = c0 + lane;
-                    if (c < a.cid_pad) {
-                        uint4* oh = reinterpret_cast<uint4*>(blk_out + c * 16);
-                        uint4* ol = reinterpret_cast<uint4*>(blk_out + (a.cid_pad + c) * 16);
-                        oh[0] = __builtin_bit_cast(uint4, lds_tr8(ds_h, dstride, 0, c0 + 16 * g, j));
-                        oh[1] = __builtin_bit_cast(uint4, lds_tr8(ds_h, dstride, 8, c0 + 16 * g, j));
-                        ol[0] = __builtin_bit_cast(uint4, lds_tr8(ds_l, dstride, 0, c0 + 16 * g, j));
-                        ol[1] = __builtin_bit_cast(uint4, lds_tr8(ds_l, dstride, 8, c0 + 16 * g, j));
+                s16x4_t qB[4];
+#pragma unroll
+                for (int f = 0; f < 4; ++f) qB[f] = lds_tr4(q_t, kRowStride, 4 * g, 16 * f, j);
+#pragma unroll
+                for (int c = 0; c < kDenseChunks; ++c)
+                    if (16 * c < a.cid_pad) {
+                        const s16x4_t aH = lds_tr4(ds_h, dstride, 4 * g, 16 * c, j), aL = lds_tr4(ds_l, dstride, 4 * g, 16 * c, j);
+#pragma unroll
+                        for (int f = 0; f < 4; ++f) {
+                            racc[c][f] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(aH, qB[f], racc[c][f], 0, 0, 0);
+                            racc[c][f] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(aL, qB[f], racc[c][f], 0, 0, 0);
+                        }
                     }
-                }
-                wave_lds_sync();   // before the next tile clears the tables
+                wave_lds_sync();   // before the next tile clears the tables and forms its bias table
             }
             float* qrow_out = a.dQ + base + (int64_t)t0 * a.sn + j;
 #pragma unroll
@@ -751,6 +800,7 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_q_tile_kernel(const TileA
         cr = ci;
         advance(ci);
     }
+    write_drel();
 }
 
 
@@ -948,112 +998,6 @@ __global__ void __launch_bounds__(kThreads, CPW == 2 ? 4 : 2) rel_grad_tile_kern
             for (int f = 0; f < 4; ++f)
 #pragma unroll
                 for (int m = 0; m < 4; ++m) dst[(16 * chunk + 4 * g + m) * kD + 16 * f + j] = acc[c][f][m] * a.scale;
-        }
-    }
-}
-
-// d_rel from the dense dS^T blocks of bwd_q_tile_kernel<.., DENSE>: per block of 32 token rows
-//   d_rel[id][f] += dS^T (A: hi and lo, read from memory in operand layout) x Q (B: the block's rows,
-//   staged in LDS, transposing reads).
-// Wavefront w owns the id chunks w, w + 8, ...; its accumulators live across the blocks the workgroup
-// walks and are written once, as this workgroup's copy, in compact-id order (summed by
-// drel_reduce_kernel in a fixed order).  The operands of the next block are requested while the
-// current one is multiplied.  A token tile past the end of a shorter sequence was not computed: its
-// half of the block counts as zero.
-template <int CPW>
-__global__ void __launch_bounds__(kThreads) rel_grad_dense_kernel(const RelGradArgs a, const bf16_t* __restrict__ dst) {
-    __shared__ __align__(16) bf16_t q_s[2][kRgRows * kRowStride];   // the block's Q rows, two buffers used alternately
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int g = lane >> 4, j = lane & 15;
-    const int nids = a.nids, nchunks = nids >> 4;
-    const int blocks_per_bh = (a.num_tiles + 1) >> 1;
-    const int total = a.BH * blocks_per_bh;
-
-    f32x4_t acc[CPW][4];
-#pragma unroll
-    for (int c = 0; c < CPW; ++c)
-#pragma unroll
-        for (int f = 0; f < 4; ++f) acc[c][f] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-
-    uint4 qpiece = make_uint4(0u, 0u, 0u, 0u);
-    uint4 ah[CPW], al[CPW];
-    auto prefetch = [&](int blk) {
-        const int bh = blk / blocks_per_bh, b = walk_pos(a.seq_len, bh, blk - bh * blocks_per_bh, blocks_per_bh), row0 = kRgRows * b;
-        const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
-        const int len = seq_length_u(a.seq_len, bh / a.H, a.n);
-        qpiece = make_uint4(0u, 0u, 0u, 0u);
-        if (threadIdx.x < kRgRows * 8) {
-            const int r = threadIdx.x >> 3, c = (threadIdx.x & 7) * 8;
-            if (row0 + r < a.n) qpiece = *reinterpret_cast<const uint4*>(a.Q + base + (int64_t)(row0 + r) * a.sn + c);
-        }
-        // this lane's rows 8g..8g+7 lie in the first (g < 2) or the second tile of the block
-        const bool live = row0 + 16 * (g >> 1) < len;
-        // [tile of the block][hi | lo][id][16 rows]
-        const bf16_t* src = dst + (((int64_t)bh * blocks_per_bh + b) * 4 + 2 * (g >> 1)) * nids * 16 + 8 * (g & 1);
-#pragma unroll
-        for (int c = 0; c < CPW; ++c) {
-            const int chunk = wave + kWaves * c;
-            ah[c] = al[c] = make_uint4(0u, 0u, 0u, 0u);
-            if (chunk < nchunks && live) {
-                const bf16_t* p = src + (16 * chunk + j) * 16;
-                ah[c] = *reinterpret_cast<const uint4*>(p);
-                al[c] = *reinterpret_cast<const uint4*>(p + nids * 16);
-            }
-        }
-    };
-    // blocks past the end of a shorter sequence add nothing and are stepped over (uniform for the workgroup)
-    auto next_block = [&](int blk) {
-        if (a.seq_len)
-            for (; blk < total; blk += gridDim.x) {
-                const int bh = blk / blocks_per_bh;
-                if (walk_pos(a.seq_len, bh, blk - bh * blocks_per_bh, blocks_per_bh) * kRgRows < seq_length_u(a.seq_len, bh / a.H, a.n)) break;
-            }
-        return blk;
-    };
-    int blk = next_block(blockIdx.x);
-    if (blk < total) prefetch(blk);
-    int buf = 0;
-    while (blk < total) {
-        bf16_t* q_b = q_s[buf];
-        if (threadIdx.x < kRgRows * 8)
-            *reinterpret_cast<uint4*>(q_b + (threadIdx.x >> 3) * kRowStride + (threadIdx.x & 7) * 8) = qpiece;
-        uint4 ch[CPW], cl[CPW];
-#pragma unroll
-        for (int c = 0; c < CPW; ++c) {
-            ch[c] = ah[c];
-            cl[c] = al[c];
-        }
-        const int blk_next = next_block(blk + gridDim.x);
-        if (blk_next < total) prefetch(blk_next);
-        __syncthreads();   // the rows are staged; the buffer written next was last read two blocks ago
-        bf16x8_t qb[4];
-#pragma unroll
-        for (int f = 0; f < 4; ++f) qb[f] = lds_tr8(q_b, kRowStride, 8 * g, 16 * f, j);
-#pragma unroll
-        for (int c = 0; c < CPW; ++c) {
-            if (wave + kWaves * c < nchunks) {
-                const bf16x8_t xh = __builtin_bit_cast(bf16x8_t, ch[c]), xl = __builtin_bit_cast(bf16x8_t, cl[c]);
-#pragma unroll
-                for (int f = 0; f < 4; ++f) {
-                    acc[c][f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xh, qb[f], acc[c][f], 0, 0, 0);
-                    acc[c][f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xl, qb[f], acc[c][f], 0, 0, 0);
-                }
-            }
-        }
-        buf ^= 1;
-        blk = blk_next;
-    }
-    // this workgroup's copy: [gridDim.x][nids][kD], compact-id order
-    float* out = a.drel_part + (int64_t)blockIdx.x * nids * kD;
-#pragma unroll
-    for (int c = 0; c < CPW; ++c) {
-        const int chunk = wave + kWaves * c;
-        if (chunk < nchunks) {
-#pragma unroll
-            for (int f = 0; f < 4; ++f)
-#pragma unroll
-                for (int m = 0; m < 4; ++m) out[(16 * chunk + 4 * g + m) * kD + 16 * f + j] = acc[c][f][m] * a.scale;
         }
     }
 }

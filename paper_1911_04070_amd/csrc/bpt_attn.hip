@@ -165,26 +165,33 @@ TilePlan plan_tiles(const bpt_graph* g, const DeviceLimits& lim, bool dense = fa
 
 void fill_tile_args(TileArgs& t, const bpt_graph* g, const AttnArgs& a, const TilePlan& tp);
 
+// grid: workgroups to launch, or 0 for as many as the device holds at once
 template <typename K>
-int launch_tiles(const char* name, K kernel, const TileArgs& t, const DeviceLimits& lim, size_t lds, hipStream_t st) {
+int launch_tiles(const char* name, K kernel, const TileArgs& t, const DeviceLimits& lim, size_t lds, hipStream_t st,
+                 int grid = 0) {
     if (lds > 65536)
         BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                     (int)lds));
-    const int grid = std::max(8, lim.cus * resident_blocks(kernel, kTileThreads, lds, lim) / 8 * 8);
+    if (grid <= 0) grid = std::max(8, lim.cus * resident_blocks(kernel, kTileThreads, lds, lim) / 8 * 8);
     BPT_LAUNCH(name, kernel, dim3(grid), dim3(kTileThreads), lds, st, t);
     BPT_HIP(hipGetLastError());
     return BPT_OK;
 }
+
+// workgroups of bwd_q_tile_kernel<.., DENSE>: its LDS allows one per compute unit; fixed, because every
+// workgroup leaves a copy of d_rel and the workspace is sized for them
+int dense_grid(const DeviceLimits& lim) { return std::max(8, lim.cus / 8 * 8); }
 
 // bf16 backward, query side of the token rows on dense tiles
 int run_bwd_q_tiles(const bpt_graph* g, const AttnArgs& a, const DeviceLimits& lim, bool dense, hipStream_t st) {
     const TilePlan tp = plan_tiles(g, lim, dense);
     TileArgs t = {};
     fill_tile_args(t, g, a, tp);
-    if (dense) {   // dS^T blocks take the place of the (w, p) pairs in the workspace
-        t.dst = reinterpret_cast<bf16_t*>(a.wp);
-        return a.drop_thr ? launch_tiles("bwd_q_tile_kernel", bwd_q_tile_kernel<true, true, true>, t, lim, tp.lds, st)
-                          : launch_tiles("bwd_q_tile_kernel", bwd_q_tile_kernel<true, false, true>, t, lim, tp.lds, st);
+    if (dense) {   // no (w, p) pairs: the kernel leaves one copy of d_rel per workgroup
+        t.drel_part = a.drel_part;
+        const int grid = dense_grid(lim);
+        return a.drop_thr ? launch_tiles("bwd_q_tile_kernel", bwd_q_tile_kernel<true, true, true>, t, lim, tp.lds, st, grid)
+                          : launch_tiles("bwd_q_tile_kernel", bwd_q_tile_kernel<true, false, true>, t, lim, tp.lds, st, grid);
     }
     if (a.drop_thr)
         return tp.rel_lds ? launch_tiles("bwd_q_tile_kernel", bwd_q_tile_kernel<true, true>, t, lim, tp.lds, st)
@@ -367,7 +374,7 @@ struct BwdPlan {
     bool drel_tile = false;   // bf16 tensors with token tiles and at most 256 ids in use: rel_grad_tile_kernel
     int drel_part_rows = 0;   // rows of one workgroup's copy of d_rel
     bool q_tiles = false;     // query side of token rows on dense tiles (bwd_q_tile_kernel)
-    bool dense_ds = false;    // ... which hands dS^T blocks (not (w, p) pairs) to rel_grad_dense_kernel
+    bool dense_ds = false;    // ... which also forms d_rel (one copy per wavefront): no (w, p) pairs, no d_rel kernel
     bool kv_tiles = false;    // key side on dense tiles of key nodes (bwd_kv_tile_kernel)
     size_t kv_lds = 0;
     int drel_ipw = 32;        // ids per wavefront: 8, 16 or 32
@@ -395,10 +402,7 @@ int plan_bwd(const bpt_graph* g, const bpt_shape_t* s, BwdPlan* p) {
             p->drel_tile = true;
             p->drel_part_rows = cids;
             p->drel_lds = rg_lds;
-            if (cids <= 16 * kWaves * 2 && plan_tiles(g, lim, true).ok) {
-                p->dense_ds = true;
-                p->drel_lds = 2 * kRgRows * kRowStride * sizeof(bf16_t);   // static, for the occupancy estimate below
-            }
+            if (cids <= 16 * kDenseChunks && plan_tiles(g, lim, true).ok) p->dense_ds = true;
         }
         if (g->ktiles.num_tasks > 0 && g->ktiles.nb_pad <= 16 * kMaxBiasChunks) {
             const int parked = std::max(0, g->ktiles.nb_pad / 16 - kRegBiasChunks);   // table operands kept in LDS
@@ -416,18 +420,17 @@ int plan_bwd(const bpt_graph* g, const bpt_shape_t* s, BwdPlan* p) {
         p->drel_grid_y = (p->drel_rows + chunk - 1) / chunk;
         blocks = (int64_t)s->B * s->H * (g->n / p->drel_block);
     }
-    // workgroups per compute unit (every workgroup writes its own copy of d_rel: no more of them than run at once;
-    // the dense kernel's registers allow two)
-    const int per_cu = p->dense_ds ? 2 : (int)std::max<size_t>(1, std::min<size_t>(4, lim.lds_cu / p->drel_lds));
+    const int per_cu = (int)std::max<size_t>(1, std::min<size_t>(4, lim.lds_cu / p->drel_lds));
     p->drel_grid_x = (int)std::max<int64_t>(1, std::min<int64_t>(blocks, (int64_t)lim.cus * per_cu / p->drel_grid_y));
+    if (p->dense_ds) p->drel_grid_x = dense_grid(lim);   // copies of d_rel: one per workgroup of bwd_q_tile_kernel
     const size_t bh = (size_t)s->B * s->H;
     size_t off = 0;
     p->off_stat = off;
     off += align_up(bh * g->num_nodes * sizeof(float2));
     p->off_wp = off;
     // (w, p) pairs: per edge of a token row in CSR order, or per slot of the token tiles
-    // or, with dense_ds, 128 bytes per (block of 32 token rows, compact id)
-    off += align_up(p->dense_ds ? bh * (size_t)((g->tiles.num_tiles + 1) / 2) * p->drel_part_rows * 128
+    // (none with dense_ds)
+    off += align_up(p->dense_ds ? 0
                                 : bh * (p->q_tiles ? (size_t)g->tiles.num_chunks * 256 : (size_t)g->num_token_edges) * sizeof(float2));
     p->off_qpart = off;
     off += align_up(bh * std::max<size_t>(std::max(g->fwd.num_part, g->fwd_span.num_part), span_partials(g)) *
@@ -520,8 +523,7 @@ int run_bwd_q(const bpt_graph* g, const BwdPlan& p, AttnArgs& a, hipStream_t st)
         t.scale = a.scale;
         t.seq_len = a.seq_len;
         if (p.dense_ds) {
-            BPT_LAUNCH("rel_grad_dense_kernel", rel_grad_dense_kernel<2>, dim3(p.drel_grid_x), dim3(kThreads), 0, st, t,
-                       reinterpret_cast<const bf16_t*>(a.wp));
+            // bwd_q_tile_kernel has left the copies of d_rel
         } else if (p.drel_part_rows <= 256) {
             if (p.drel_lds > 65536)
                 BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rel_grad_tile_kernel<2>),
