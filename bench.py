@@ -28,16 +28,15 @@ HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
 # workload; the runs and their commands are in profiles/.  None where not measured.
 MEASURED_TRAFFIC = {
     "lm": {  # profiles/lm_n8192_k8_causal_bf16_kernels.md
-        "bwd_kv_tile_kernel": int((223688.0 * 2.0 + 279937.0) * 1024),
-        "bwd_q_tile_kernel": int((133085.0 * 2.0 + 165975.0) * 1024),
-        "rel_grad_dense_kernel": int((65576.0 * 2.0 + 24576.0) * 1024),
-        "fwd_tile_kernel": int((117165.0 * 2.0 + 33874.0) * 1024),
-        "bwd_q_span_tile_kernel": int((67578.0 * 2.0 + 99730.0) * 1024),
-        "fwd_span_tile_kernel": int((49577.0 * 2.0 + 49977.0) * 1024),
+        "bwd_kv_tile_kernel": int((223916.0 * 2.0 + 279937.0) * 1024),
+        "bwd_q_tile_kernel": int((132764.0 * 2.0 + 73782.0) * 1024),
+        "fwd_tile_kernel": int((117007.0 * 2.0 + 33871.0) * 1024),
+        "bwd_q_span_tile_kernel": int((67579.0 * 2.0 + 99727.0) * 1024),
+        "fwd_span_tile_kernel": int((49581.0 * 2.0 + 49975.0) * 1024),
     },
 }
 # HBM bytes of one whole step (all kernels, same counters and scaling)
-MEASURED_STEP_TRAFFIC = {"lm": 2126708768}
+MEASURED_STEP_TRAFFIC = {"lm": 1854641472}
 
 
 def parse():
