@@ -338,24 +338,31 @@ __global__ void __launch_bounds__(256) kv_tile_merge_kernel(const KeyArgs a, con
                                                             int first_zero) {
     const int merge_blocks = a.BH * num_multi;
     if ((int)blockIdx.x >= merge_blocks) {
-        // zero rows: without seq_len the nodes from first_zero on, 64 threads per row; with seq_len
-        // every node is looked at, 16 threads per row, and those a shorter sequence does not keep
-        // (which the tile kernel steps over) are written as well
-        const int row0 = a.seq_len ? 0 : first_zero, rows = a.N - row0;
-        const int per_row = a.seq_len ? 16 : 64;
-        const int64_t i = (int64_t)(blockIdx.x - merge_blocks) * blockDim.x + threadIdx.x;
-        if (i >= (int64_t)a.BH * rows * per_row) return;
-        const int64_t rr = i / per_row;
-        const int bh = (int)(rr / rows), row = row0 + (int)(rr - (int64_t)bh * rows);
-        const int64_t at = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh + (int64_t)row * a.sn;
-        if (!a.seq_len) {
-            const int f = (int)(i & 63);
-            a.dK[at + f] = 0.f;
-            a.dV[at + f] = 0.f;
-        } else if (row >= first_zero || node_first_token(row, 31 - __clz(a.n)) >= seq_length(a.seq_len, bh / a.H, a.n)) {
-            const int f = (int)(i & 15) * 4;
-            *reinterpret_cast<float4*>(a.dK + at + f) = make_float4(0.f, 0.f, 0.f, 0.f);
-            *reinterpret_cast<float4*>(a.dV + at + f) = make_float4(0.f, 0.f, 0.f, 0.f);
+        // zero rows: without seq_len the nodes from first_zero on; with seq_len also those a shorter sequence
+        // does not keep (which the tile kernel steps over).  A wavefront looks at 64 consecutive nodes, one
+        // per lane, and then writes the rows found two at a time: 16 lanes x 16 bytes for each of dK and dV
+        // of a row.
+        const int row0 = a.seq_len ? 0 : (first_zero & ~63), waves_per_bh = (a.N - row0 + 63) >> 6;
+        const int64_t gw = ((int64_t)(blockIdx.x - merge_blocks) * blockDim.x + threadIdx.x) >> 6;
+        if (gw >= (int64_t)a.BH * waves_per_bh) return;
+        const int lane = threadIdx.x & 63;
+        const int bh = (int)(gw / waves_per_bh), first = row0 + 64 * (int)(gw - (int64_t)bh * waves_per_bh);
+        const int row = first + lane;
+        bool gone = row < a.N && row >= first_zero;
+        if (a.seq_len && row < a.N)
+            gone = gone || node_first_token(row, 31 - __clz(a.n)) >= seq_length(a.seq_len, bh / a.H, a.n);
+        uint64_t todo = __ballot(gone);
+        const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
+        while (todo) {   // wave-uniform
+            const int ra = __builtin_ctzll(todo);
+            todo &= todo - 1;
+            const int rb = todo ? __builtin_ctzll(todo) : -1;
+            if (todo) todo &= todo - 1;
+            const int r = lane < 32 ? ra : rb;
+            if (r >= 0) {
+                float* dst = ((lane & 16) ? a.dV : a.dK) + base + (int64_t)(first + r) * a.sn + 4 * (lane & 15);
+                *reinterpret_cast<float4*>(dst) = make_float4(0.f, 0.f, 0.f, 0.f);
+            }
         }
         return;
     }

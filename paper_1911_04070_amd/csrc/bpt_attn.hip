@@ -637,8 +637,9 @@ int run_bwd_kv_tiles(const bpt_graph* g, const BwdPlan& p, const AttnArgs& a, co
         default: break;
     }
     if (rc) return rc;
-    // threads of the zero pass of kv_tile_merge_kernel: 64 per uncovered row, or 16 per row of the graph
-    const int64_t zero_elems = a.seq_len ? (int64_t)a.BH * a.N * 16 : (int64_t)a.BH * (a.N - kt.first_uncovered) * kD;
+    // threads of the zero pass of kv_tile_merge_kernel: one per node it has to look at, in wavefronts of 64 nodes
+    const int zero_row0 = a.seq_len ? 0 : (kt.first_uncovered & ~63);
+    const int64_t zero_elems = (int64_t)a.BH * ((a.N - zero_row0 + 63) / 64) * 64;
     const int64_t blocks = (int64_t)a.BH * kt.num_multi + (zero_elems + 255) / 256;
     if (blocks > 0) {
         BPT_LAUNCH("kv_tile_merge_kernel", kv_tile_merge_kernel, dim3((unsigned)blocks), dim3(256), 0, st, t, kt.multi_tile,
