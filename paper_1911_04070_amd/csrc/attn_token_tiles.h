@@ -135,6 +135,48 @@ __device__ __forceinline__ void mask_bias(const TileArgs& a, float* bias_s, int 
     }
 }
 
+// Batches of sequences of different lengths: entry b keeps its first ceil(len_b / 16) token tiles, so the
+// tiles that exist can be numbered in closed form from a prefix sum over the batch, head-major --
+// i -> (head i / S, entry b with pref[b] <= i % S < pref[b + 1], tile i % S - pref[b]), S = pref[B] -- and
+// so can the ones that do not (entry b has num_tiles - count_b of them, after the kept ones).  A
+// kernel that walks these numbers instead of all (batch, head, tile) triples gives every wavefront
+// the same number of tiles to compute, whatever the lengths.  Up to kMaxLenBatch entries.
+constexpr int kMaxLenBatch = 256;
+// whole workgroup; pref[0 .. B] in LDS; ends with a barrier
+__device__ __forceinline__ void live_tiles_prefix(int* pref, const int32_t* seq_len, int B, int n, int num_tiles) {
+    if (threadIdx.x < 64) {
+        int carry = 0;
+        for (int b0 = 0; b0 < B; b0 += 64) {
+            const int b = b0 + (int)threadIdx.x;
+            const int cnt = b < B ? min(num_tiles, (min(max(seq_len[b], 0), n) + 15) >> 4) : 0;
+            int incl = cnt;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const int up = __shfl_up(incl, d);
+                if ((int)threadIdx.x >= d) incl += up;
+            }
+            if (b < B) pref[b] = carry + incl - cnt;
+            carry += __shfl(incl, 63);
+        }
+        if (threadIdx.x == 0) pref[B] = carry;
+    }
+    __syncthreads();
+}
+// the idx-th tile that exists (dead == false) or that does not (dead == true); wave-uniform arguments
+__device__ __forceinline__ void nth_tile(const int* pref, int B, int H, int num_tiles, bool dead, int idx, int& bh, int& tile) {
+    const int per_head = dead ? B * num_tiles - pref[B] : pref[B];
+    const int h = idx / per_head, r = idx - h * per_head;
+    int lo = 0, hi = B - 1;   // the last entry whose tiles begin at or before r
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        const int start = dead ? mid * num_tiles - pref[mid] : pref[mid];
+        if (start <= r) lo = mid; else hi = mid - 1;
+    }
+    const int start = dead ? lo * num_tiles - pref[lo] : pref[lo];
+    bh = lo * H + h;
+    tile = dead ? (pref[lo + 1] - pref[lo]) + (r - start) : r - start;
+}
+
 // Position of a wavefront in its sequence of (token tile, pair of chunks); wave-uniform.
 struct TileCursor {
     int t, pair, npairs, cp0, bh, tile;
@@ -177,7 +219,32 @@ __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArg
     const rsrc_t rC = make_rsrc(a.cols, (uint32_t)a.num_chunks * 64u);   // [chunks][16] int32
     const rsrc_t rM = make_rsrc(a.map, (uint32_t)a.num_chunks * 512u);   // [chunks][16][16] int16
     const int groups_per_bh = (a.num_tiles + kTileWaves - 1) / kTileWaves;
-    const TileWalk w(a.BH * groups_per_bh);
+    // sequences of different lengths: walk the tiles that exist, and first write the zero rows of the others
+    __shared__ int pref_s[kMaxLenBatch + 1];
+    const int nbatch = a.BH / a.H;
+    const bool compact = a.seq_len && nbatch <= kMaxLenBatch;
+    int live_total = 0;
+    auto zero_rows = [&](int bh, int tile) {   // out and lse of a tile past the end of its sequence
+        const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
+        bf16_t* orow = a.out + base + (int64_t)(tile * 16 + r8) * a.sn + piece * 8;
+        *reinterpret_cast<uint4*>(orow) = make_uint4(0u, 0u, 0u, 0u);
+        *reinterpret_cast<uint4*>(orow + 8 * a.sn) = make_uint4(0u, 0u, 0u, 0u);
+        if (lane < 16) a.lse[(int64_t)bh * a.N + tile * 16 + lane] = 0.f;
+    };
+    if (compact) {
+        live_tiles_prefix(pref_s, a.seq_len, nbatch, a.n, a.num_tiles);
+        live_total = a.H * pref_s[nbatch];
+        const int dead_total = a.BH * a.num_tiles - live_total;
+        for (TileWalk wd((dead_total + kTileWaves - 1) / kTileWaves); wd.t < wd.t_end; wd.t += wd.step) {
+            const int idx = wd.t * kTileWaves + wave;
+            if (idx < dead_total) {
+                int bh, tile;
+                nth_tile(pref_s, nbatch, a.H, a.num_tiles, true, idx, bh, tile);
+                zero_rows(bh, tile);
+            }
+        }
+    }
+    const TileWalk w(compact ? (live_total + kTileWaves - 1) / kTileWaves : a.BH * groups_per_bh);
 
     // One sequence of pairs of chunks through the wavefront's tiles, software pipelined as in
     // bwd_q_tile_kernel: `cc` is computed, the rows of `cr` and the ids of `ci` are in flight.
@@ -188,17 +255,23 @@ __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArg
         c.valid = false;
         c.pair = 0;
         c.npairs = 1;
+        if (compact) {   // the next tile that exists; the walk covers nothing else
+            const int idx = c.t * kTileWaves + wave;
+            if (c.t < w.t_end && idx < live_total) {
+                nth_tile(pref_s, nbatch, a.H, a.num_tiles, false, idx, c.bh, c.tile);
+                c.cp0 = a.chunk_ptr[c.tile];
+                c.npairs = (a.chunk_ptr[c.tile + 1] - c.cp0) >> 1;
+                c.valid = true;
+            }
+            return;
+        }
         for (; c.t < w.t_end; c.t += w.step) {
             const int slab = c.t / groups_per_bh;
             c.bh = walk_bh(a.seq_len, slab, a.BH, a.H);
             c.tile = walk_pos(a.seq_len, slab, c.t - slab * groups_per_bh, groups_per_bh) * kTileWaves + wave;
             if (c.tile >= a.num_tiles) continue;
             if (a.seq_len && c.tile * 16 >= seq_length_u(a.seq_len, c.bh / a.H, a.n)) {
-                const int64_t base = (int64_t)(c.bh / a.H) * a.sb + (int64_t)(c.bh % a.H) * a.sh;
-                bf16_t* orow = a.out + base + (int64_t)(c.tile * 16 + r8) * a.sn + piece * 8;
-                *reinterpret_cast<uint4*>(orow) = make_uint4(0u, 0u, 0u, 0u);
-                *reinterpret_cast<uint4*>(orow + 8 * a.sn) = make_uint4(0u, 0u, 0u, 0u);
-                if (lane < 16) a.lse[(int64_t)c.bh * a.N + c.tile * 16 + lane] = 0.f;
+                zero_rows(c.bh, c.tile);
                 continue;
             }
             c.cp0 = a.chunk_ptr[c.tile];
@@ -463,7 +536,35 @@ __global__ void __launch_bounds__(kTileThreads, DENSE ? 1 : 2) bwd_q_tile_kernel
     const rsrc_t rC = make_rsrc(a.cols, (uint32_t)a.num_chunks * 64u);
     const rsrc_t rM = make_rsrc(a.map, (uint32_t)a.num_chunks * 512u);
     const int groups_per_bh = (a.num_tiles + kTileWaves - 1) / kTileWaves;
-    const TileWalk w(a.BH * groups_per_bh);
+    // sequences of different lengths: walk the tiles that exist, and first write the zero rows of the others
+    __shared__ int pref_s[kMaxLenBatch + 1];
+    const int nbatch = a.BH / a.H;
+    const bool compact = a.seq_len && nbatch <= kMaxLenBatch;
+    int live_total = 0;
+    auto zero_rows = [&](int bh, int tile) {   // dQ of a tile past the end of its sequence; `stat` switches its rows off on the key side
+        const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
+        float* qrow = a.dQ + base + (int64_t)(tile * 16 + r8) * a.sn + piece * 8;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            *reinterpret_cast<float4*>(qrow + (int64_t)8 * h * a.sn) = make_float4(0.f, 0.f, 0.f, 0.f);
+            *reinterpret_cast<float4*>(qrow + (int64_t)8 * h * a.sn + 4) = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        if (lane < 16) a.stat[(int64_t)bh * a.N + tile * 16 + lane] = make_float2(kLseGone, 0.f);
+    };
+    if (compact) {
+        live_tiles_prefix(pref_s, a.seq_len, nbatch, a.n, a.num_tiles);
+        live_total = a.H * pref_s[nbatch];
+        const int dead_total = a.BH * a.num_tiles - live_total;
+        for (TileWalk wd((dead_total + kTileWaves - 1) / kTileWaves); wd.t < wd.t_end; wd.t += wd.step) {
+            const int idx = wd.t * kTileWaves + wave;
+            if (idx < dead_total) {
+                int bh, tile;
+                nth_tile(pref_s, nbatch, a.H, a.num_tiles, true, idx, bh, tile);
+                zero_rows(bh, tile);
+            }
+        }
+    }
+    const TileWalk w(compact ? (live_total + kTileWaves - 1) / kTileWaves : a.BH * groups_per_bh);
 
     // The wavefront's work is one sequence of pairs of chunks running through its tiles.
     // Three positions move along it: `cc` is computed, the rows of `cr` (one pair ahead) are
@@ -475,20 +576,23 @@ __global__ void __launch_bounds__(kTileThreads, DENSE ? 1 : 2) bwd_q_tile_kernel
         c.valid = false;
         c.pair = 0;
         c.npairs = 1;
+        if (compact) {   // the next tile that exists; the walk covers nothing else
+            const int idx = c.t * kTileWaves + wave;
+            if (c.t < w.t_end && idx < live_total) {
+                nth_tile(pref_s, nbatch, a.H, a.num_tiles, false, idx, c.bh, c.tile);
+                c.cp0 = uniform_i32(a.chunk_ptr, c.tile);
+                c.npairs = (uniform_i32(a.chunk_ptr, c.tile + 1) - c.cp0) >> 1;
+                c.valid = true;
+            }
+            return;
+        }
         for (; c.t < w.t_end; c.t += w.step) {
             const int slab = c.t / groups_per_bh;
             c.bh = walk_bh(a.seq_len, slab, a.BH, a.H);
             c.tile = walk_pos(a.seq_len, slab, c.t - slab * groups_per_bh, groups_per_bh) * kTileWaves + wave;
             if (c.tile >= a.num_tiles) continue;
             if (a.seq_len && c.tile * 16 >= seq_length_u(a.seq_len, c.bh / a.H, a.n)) {
-                const int64_t base = (int64_t)(c.bh / a.H) * a.sb + (int64_t)(c.bh % a.H) * a.sh;
-                float* qrow = a.dQ + base + (int64_t)(c.tile * 16 + r8) * a.sn + piece * 8;
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    *reinterpret_cast<float4*>(qrow + (int64_t)8 * h * a.sn) = make_float4(0.f, 0.f, 0.f, 0.f);
-                    *reinterpret_cast<float4*>(qrow + (int64_t)8 * h * a.sn + 4) = make_float4(0.f, 0.f, 0.f, 0.f);
-                }
-                if (lane < 16) a.stat[(int64_t)c.bh * a.N + c.tile * 16 + lane] = make_float2(kLseGone, 0.f);
+                zero_rows(c.bh, c.tile);
                 continue;
             }
             c.cp0 = uniform_i32(a.chunk_ptr, c.tile);

@@ -156,10 +156,11 @@ TilePlan plan_tiles(const bpt_graph* g, const DeviceLimits& lim, bool dense = fa
                         (size_t)kTileWaves * 64 * kRowStride * sizeof(bf16_t) +
                         (size_t)t.cid_pad * sizeof(int32_t) +   // relative-position ids of the compact ids (dropout)
                         (dense ? (size_t)kTileWaves * 32 * t.bias_stride * sizeof(float) : 0);
-    t.rel_lds = rel + rest <= lim.lds;
+    const size_t room = lim.lds - (kMaxLenBatch + 1) * sizeof(int32_t) - 16;   // the kernels' static LDS (prefix sums of a length mix)
+    t.rel_lds = rel + rest <= room;
     t.lds = t.rel_lds ? rel + rest : rest;
     // (dense: dS of a tile, bf16 hi and lo with 16 bytes of padding per row, has to fit a wavefront's row buffers)
-    t.ok = dense ? t.rel_lds && 64 * (t.cid_pad + 8) <= 64 * kRowStride * (int)sizeof(bf16_t) : t.lds <= lim.lds;
+    t.ok = dense ? t.rel_lds && 64 * (t.cid_pad + 8) <= 64 * kRowStride * (int)sizeof(bf16_t) : t.lds <= room;
     return t;
 }
 
