@@ -252,6 +252,15 @@ def test_sequences_of_different_lengths(dtype, n, k, causal, H, lengths):
     run_lengths_case(w, lengths)
 
 
+def test_lengths_of_a_batch_of_300():
+    # more entries than the token-tile kernels number in closed form (256): the walk over all tiles with its
+    # skips takes over; and 200, which they do number
+    for B in (300, 200):
+        rng = np.random.default_rng(300 + B)
+        lengths = [int(v) for v in rng.integers(0, 65, size=B)]
+        run_lengths_case(Workload("batch%d" % B, 23, 64, 2, False, B, 1, 64, "bf16", True), lengths)
+
+
 def test_lengths_with_node_major_memory_and_many_ids():
     # [B,N,H,D] memory through the strides, and a density whose key tiles park table operands in LDS
     w = Workload("lengths_dense", 23, 1024, 64, False, 2, 2, 64, "bf16", True)
