@@ -487,8 +487,8 @@ __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArg
 // Per tile: S^T and dP^T = V_chunk x dO^T on the matrix cores, p = exp2(s - lse),
 // w = p dP, delta = sum w; then, with K staged in LDS as the B operand,
 //   dQ_K = scale * (W K_U - delta * P K_U)       (the key part of dQ; lse is known, so
-// no online softmax and no second pass).  (w, p) of every edge goes to `wp` in CSR
-// order for the d_rel kernel, which also adds the relative-position part of dQ.
+// no online softmax and no second pass).  Without DENSE, (w, p) of every tile slot goes to `wp` in
+// tile order for rel_grad_tile_kernel, which also adds the relative-position part of dQ.
 // REL_LDS: the compact relative-position table is staged in LDS; otherwise (large tables) its rows
 // are read from memory when a tile forms its bias table.
 // DENSE (needs REL_LDS and cid_pad a multiple of 32): a tile's w = p dP and p are not stored per slot
