@@ -122,6 +122,18 @@ __global__ void __launch_bounds__(kTileThreads) fwd_span_tile_kernel(const SpanA
         span_block_gone(a, bh, blk, t0, nblk, nanc, base, true, lane);
         return;
     }
+    // the query rows of all three groups are asked for together with the block's K and V: one round trip
+    // to memory per block instead of four
+    bf16x8_t qall[3][2];
+#pragma unroll
+    for (int grp = 0; grp < 3; ++grp) {
+        int level, loc;
+        bool valid;
+        span_slot(min(grp, ngroups - 1), j, a.L, level, loc, valid);
+        const bf16_t* qrow = a.Q + base + (int64_t)(span_level_offset(a.n, level) + (t0 >> level) + loc) * a.sn + 16 * g;
+        qall[grp][0] = *reinterpret_cast<const bf16x8_t*>(qrow);
+        qall[grp][1] = *reinterpret_cast<const bf16x8_t*>(qrow + 8);
+    }
     bf16x8_t ka[2][2];
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
@@ -137,14 +149,14 @@ __global__ void __launch_bounds__(kTileThreads) fwd_span_tile_kernel(const SpanA
     }
     wave_lds_sync();
 
-    for (int grp = 0; grp < ngroups; ++grp) {
+#pragma unroll
+    for (int grp = 0; grp < 3; ++grp) {
+        if (grp >= ngroups) break;   // wave-uniform
         int level, loc;
         bool valid;
         span_slot(grp, j, a.L, level, loc, valid);
         const int node = span_level_offset(a.n, level) + (t0 >> level) + loc;
-        const bf16_t* qrow = a.Q + base + (int64_t)node * a.sn + 16 * g;
-        const bf16x8_t qb0 = *reinterpret_cast<const bf16x8_t*>(qrow);
-        const bf16x8_t qb1 = *reinterpret_cast<const bf16x8_t*>(qrow + 8);
+        const bf16x8_t qb0 = qall[grp][0], qb1 = qall[grp][1];
         const float shift = span_shift(a, level, g, qb0, qb1, qscale);
         float p[2][4], m = kNegBig;
 #pragma unroll
@@ -369,6 +381,24 @@ __global__ void __launch_bounds__(kTileThreads, 3) bwd_q_span_tile_kernel(const 
         span_block_gone(a, bh, blk, t0, nblk, nanc, base, false, lane);
         return;
     }
+    // the Q and dO rows and the lse of all three groups are asked for together with the block's K and V:
+    // one round trip to memory per block instead of four
+    bf16x8_t qall[3][2], gall[3][2];
+    float lall[3];
+#pragma unroll
+    for (int grp = 0; grp < 3; ++grp) {
+        int level, loc;
+        bool valid;
+        span_slot(min(grp, ngroups - 1), j, a.L, level, loc, valid);
+        const int node = span_level_offset(a.n, level) + (t0 >> level) + loc;
+        const bf16_t* qrow = a.Q + base + (int64_t)node * a.sn + 16 * g;
+        const bf16_t* grow = a.dout + base + (int64_t)node * a.sn + 16 * g;
+        qall[grp][0] = *reinterpret_cast<const bf16x8_t*>(qrow);
+        qall[grp][1] = *reinterpret_cast<const bf16x8_t*>(qrow + 8);
+        gall[grp][0] = *reinterpret_cast<const bf16x8_t*>(grow);
+        gall[grp][1] = *reinterpret_cast<const bf16x8_t*>(grow + 8);
+        lall[grp] = a.lse_r[(int64_t)bh * a.N + node];
+    }
     bf16x8_t ka[2][2], va[2][2];
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
@@ -389,18 +419,15 @@ __global__ void __launch_bounds__(kTileThreads, 3) bwd_q_span_tile_kernel(const 
 #pragma unroll
     for (int f = 0; f < 4; ++f) kB[f] = lds_transposed_b(k_s, kVStride, f, g, j);
 
-    for (int grp = 0; grp < ngroups; ++grp) {
+#pragma unroll
+    for (int grp = 0; grp < 3; ++grp) {
+        if (grp >= ngroups) break;   // wave-uniform
         int level, loc;
         bool valid;
         span_slot(grp, j, a.L, level, loc, valid);
         const int node = span_level_offset(a.n, level) + (t0 >> level) + loc;
-        const bf16_t* qrow = a.Q + base + (int64_t)node * a.sn + 16 * g;
-        const bf16_t* grow = a.dout + base + (int64_t)node * a.sn + 16 * g;
-        const bf16x8_t qb0 = *reinterpret_cast<const bf16x8_t*>(qrow);
-        const bf16x8_t qb1 = *reinterpret_cast<const bf16x8_t*>(qrow + 8);
-        const bf16x8_t gb0 = *reinterpret_cast<const bf16x8_t*>(grow);
-        const bf16x8_t gb1 = *reinterpret_cast<const bf16x8_t*>(grow + 8);
-        const float lse2 = a.lse_r[(int64_t)bh * a.N + node] * kLog2e;
+        const bf16x8_t qb0 = qall[grp][0], qb1 = qall[grp][1], gb0 = gall[grp][0], gb1 = gall[grp][1];
+        const float lse2 = lall[grp] * kLog2e;
         const float shift = span_shift(a, level, g, qb0, qb1, qscale);
         const uint32_t rowh = DROP ? drop_row_hash(drop_bh_hash(a.drop_seed, bh), node) : 0u;
         float p[2][4], wgt[2][4], dl = 0.f;
