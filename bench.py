@@ -52,10 +52,73 @@ def parse():
     ap.add_argument("--layer", action="store_true",
                     help="time the forward of one whole graph layer (projections, attention, FFN, normalisations; "
                          "d_ff = 4 d) of the workload's shape instead of the attention path")
+    ap.add_argument("--layers", type=int, default=1,
+                    help="with --layer: the update of the graph over this many layers, from the embeddings to the "
+                         "token rows (causal workloads) or the root's row of the last layer, forward + backward")
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="only run a plain device-to-device copy of this many MiB (10 times) and exit: the known "
                          "traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
     return ap.parse_args()
+
+
+def layer_params(torch, rnd, d, d_ff):
+    p = {k_: rnd(d, d, s=d ** -0.5).to(torch.bfloat16) for k_ in ("Wq", "Wk", "Wv", "Wo")}
+    p["W1"] = rnd(d, d_ff, s=d ** -0.5).to(torch.bfloat16)
+    p["W2"] = rnd(d_ff, d, s=d_ff ** -0.5).to(torch.bfloat16)
+    p.update(b1=rnd(d_ff, s=0.1), b2=rnd(d, s=0.1), g1=1 + rnd(d, s=0.1), beta1=rnd(d, s=0.1), g2=1 + rnd(d, s=0.1),
+             beta2=rnd(d, s=0.1))
+    return p
+
+
+def bench_stack(args, w, bpt, torch, np):
+    """Forward + backward of the update of the graph (Sec. 3.3) over --layers layers on the workload's shape: from
+    the embeddings [B, n, d] to the token rows (causal workloads: language modelling) or the root's row
+    (classification) of the last layer and back; d = heads * 64, d_ff = 4 d, random bf16 weights."""
+    from paper_1911_04070_amd.workloads import make_lengths
+    d, d_ff, layers = w.H * w.D, 4 * w.H * w.D, args.layers
+    g = bpt.bpt_build_graph(w.n, w.k, w.causal)
+    gen = torch.Generator(device="cuda").manual_seed(1911 + w.index)
+    rnd = lambda *shape, s=1.0: (s * torch.randn(*shape, device="cuda", generator=gen))
+    E = rnd(w.B, w.n, d).to(torch.bfloat16)
+    rels = [rnd(g.num_levels, g.rel_width, w.D, s=0.02).to(torch.bfloat16) for _ in range(layers)]
+    params = [layer_params(torch, rnd, d, d_ff) for _ in range(layers)]
+    lens_d = torch.from_numpy(make_lengths(w)).cuda() if w.length_mix else None
+    tokens_out = bool(w.causal)
+    d_root = None if tokens_out else rnd(w.B, d).to(torch.bfloat16)
+    d_tokens = rnd(w.B, w.n, d).to(torch.bfloat16) if tokens_out else None
+    fws, bws = bpt.stack_workspace_bytes(g, w.B, w.H, d_ff, layers)
+    ws = torch.empty(fws + 256, dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(bws + 256, dtype=torch.uint8, device="cuda")
+    fwd = lambda: bpt.bpt_stack_fwd(g, E, rels, params, w.H, scale=w.scale, seq_len=lens_d, want_root=not tokens_out,
+                                    want_tokens=tokens_out, workspace=ws)
+    bwd = lambda: bpt.bpt_stack_bwd(g, E, rels, params, w.H, ws, d_root, d_tokens, scale=w.scale, seq_len=lens_d,
+                                    workspace=ws_b)
+
+    def wall_ms(fn):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / args.steps
+
+    for _ in range(args.warmup + 2):
+        fwd()
+        bwd()
+    ms = wall_ms(lambda: (fwd(), bwd()))
+    ms_fwd = wall_ms(fwd)
+    rows = w.B * g.num_nodes
+    flops = layers * 3 * 2.0 * rows * (4 * d * d + 2 * d * d_ff)
+    print(json.dumps({
+        "metric": "BPT graph update fwd+bwd tokens/sec", "value": round(w.B * w.n / (ms * 1e-3), 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
+        "dtype": "bf16", "data": "synthetic", "vs_baseline": None, "forward_ms": round(ms_fwd, 4),
+        "config": {"workload": "%s+%d layers" % (w.name, layers), "n": w.n, "k": w.k, "causal": w.causal, "batch": w.B,
+                   "heads": w.H, "d_model": d, "d_ff": d_ff, "layers": layers, "node_rows": rows,
+                   "output": "tokens" if tokens_out else "root"},
+        "dense_TFLOPs": round(flops / (ms * 1e-3) / 1e12, 1),
+        "workspace_GB": round((fws + bws) / 1e9, 2),
+    }), flush=True)
 
 
 def bench_layer(args, w, bpt, torch, np):
@@ -69,11 +132,7 @@ def bench_layer(args, w, bpt, torch, np):
     X = rnd(w.B, g.num_nodes, d).to(torch.bfloat16)
     X[:, w.n:] = 0                                            # span nodes start from zero
     R = rnd(g.num_levels, g.rel_width, w.D, s=0.02).to(torch.bfloat16)
-    p = {k_: rnd(d, d, s=d ** -0.5).to(torch.bfloat16) for k_ in ("Wq", "Wk", "Wv", "Wo")}
-    p["W1"] = rnd(d, d_ff, s=d ** -0.5).to(torch.bfloat16)
-    p["W2"] = rnd(d_ff, d, s=d_ff ** -0.5).to(torch.bfloat16)
-    p.update(b1=rnd(d_ff, s=0.1), b2=rnd(d, s=0.1), g1=1 + rnd(d, s=0.1), beta1=rnd(d, s=0.1), g2=1 + rnd(d, s=0.1),
-             beta2=rnd(d, s=0.1))
+    p = layer_params(torch, rnd, d, d_ff)
     lens_d = torch.from_numpy(make_lengths(w)).cuda() if w.length_mix else None
     Y = torch.empty_like(X)
     dY = rnd(w.B, g.num_nodes, d).to(torch.bfloat16)
@@ -152,7 +211,7 @@ def main():
     w = WORKLOADS[args.workload]
     torch.cuda.set_device(0)
     if args.layer:
-        return bench_layer(args, w, bpt, torch, np)
+        return (bench_stack if args.layers > 1 else bench_layer)(args, w, bpt, torch, np)
     tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
     bytes_scale = 1.0 if w.dtype == "bf16" else 2.0
 

@@ -240,6 +240,35 @@ int bpt_layer_bwd(const bpt_graph_t* g, int32_t B, int32_t H, float scale, const
                   const void* dY, void* dX, float* d_rel, const bpt_layer_grads_t* grads, void* workspace,
                   size_t workspace_bytes, void* stream);
 
+/* Sec. 3.3, the update of the graph from its initial states to its output, bf16: the states before
+ * the first layer are the embeddings E [B][n][d] on the token rows and zero on the span rows;
+ * layer l = 0 .. num_layers-1 is bpt_layer_fwd with its own parameters p[l] and its own
+ * relative-position table rel[l] (p and rel are host arrays of num_layers entries; every
+ * p[l].d_ff must be the same); the output is the root's row of the last states, root [B][d],
+ * and / or their token rows, tokens [B][n][d] (one of the two may be NULL).  With seq_len, the
+ * root is still node 2n-2 (it is kept by every sequence with a token) and token rows past a
+ * sequence's end hold unspecified values.  The workspace (bpt_stack_fwd_workspace bytes of
+ * device memory) keeps every layer's input states and activations for bpt_stack_bwd; nothing
+ * is allocated beyond what bpt_layer_fwd states.  num_layers <= 256. */
+size_t bpt_stack_fwd_workspace(const bpt_graph_t* g, int32_t B, int32_t H, int32_t d_ff, int32_t num_layers);
+int bpt_stack_fwd(const bpt_graph_t* g, int32_t B, int32_t H, int32_t num_layers, float scale, const int32_t* seq_len,
+                  const void* const* rel, const void* E, const bpt_layer_params_t* p, void* root, void* tokens,
+                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* Backward of bpt_stack_fwd: given the gradient of a scalar with respect to the outputs, d_root
+ * [B][d] and / or d_tokens [B][n][d] in bf16 (a NULL one counts as zero; not both), runs
+ * bpt_layer_bwd from the last layer to the first and writes dE [B][n][d] bf16 (the gradient
+ * with respect to the embeddings), d_rel[l] and grads[l] for every layer (host arrays of
+ * num_layers entries, each as for bpt_layer_bwd).  The other arguments must be those of the
+ * forward call and fwd_workspace its workspace, unchanged.  workspace: at least
+ * bpt_stack_bwd_workspace bytes of device memory (it does not grow with num_layers); nothing
+ * is allocated. */
+size_t bpt_stack_bwd_workspace(const bpt_graph_t* g, int32_t B, int32_t H, int32_t d_ff);
+int bpt_stack_bwd(const bpt_graph_t* g, int32_t B, int32_t H, int32_t num_layers, float scale, const int32_t* seq_len,
+                  const void* const* rel, const bpt_layer_params_t* p, const void* fwd_workspace,
+                  size_t fwd_workspace_bytes, const void* d_root, const void* d_tokens, void* dE, float* const* d_rel,
+                  const bpt_layer_grads_t* grads, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Sec. 3.2 with the rule for shorter sequences stated at the top of this header: the number
  * of edges of the graph over n tokens with density k that a sequence of len tokens keeps
  * (0 <= len <= n; len == n gives the graph's own edge count).  Host arithmetic only, no

@@ -125,3 +125,37 @@ def layer_backward(n, k, causal, heads, X, Rel, p, dY, scale, eps=1e-5, lengths=
         dX += gj @ W[name].T
     res["dX"] = dX
     return res
+
+
+def initial_states(n: int, E: np.ndarray) -> np.ndarray:
+    """Sec. 3.3: token nodes start from their embeddings E [B, n, d], span nodes from zero -> [B, 2n-1, d]."""
+    B, _, d = E.shape
+    H0 = np.zeros((B, 2 * n - 1, d), dtype=np.float64)
+    H0[:, :n] = E
+    return H0
+
+
+def stack_forward(n, k, causal, heads, E, Rels, params, scale, eps=1e-5, lengths=None):
+    """Sec. 3.3, the update of the graph: H^0 = initial states, H^i = layer_i(H^{i-1}) with each layer's own
+    parameters params[i] and relative-position table Rels[i]; the output is the root's row of the last states
+    (node 2n-2) and their token rows.  Returns (root [B, d], tokens [B, n, d], [H^0 .. H^layers])."""
+    states = [initial_states(n, E)]
+    for Rel, p in zip(Rels, params):
+        states.append(layer_forward(n, k, causal, heads, states[-1], Rel, p, scale, eps, lengths))
+    last = states[-1]
+    return last[:, 2 * n - 2], last[:, :n], states
+
+
+def stack_backward(n, k, causal, heads, E, Rels, params, d_root, d_tokens, scale, eps=1e-5, lengths=None):
+    """Gradient of sum(root * d_root) + sum(tokens * d_tokens) of `stack_forward` with respect to the embeddings
+    and every layer's table and parameters: `layer_backward` from the last layer to the first.  Returns (dE
+    [B, n, d], list of the layers' gradient dicts, first layer first)."""
+    _, _, states = stack_forward(n, k, causal, heads, E, Rels, params, scale, eps, lengths)
+    dH = np.zeros_like(states[-1])
+    dH[:, 2 * n - 2] = d_root
+    dH[:, :n] = d_tokens
+    grads = [None] * len(params)
+    for i in range(len(params) - 1, -1, -1):
+        grads[i] = layer_backward(n, k, causal, heads, states[i], Rels[i], params[i], dH, scale, eps, lengths)
+        dH = grads[i]["dX"]
+    return dH[:, :n], grads

@@ -24,6 +24,7 @@ EXPORTS = [
     "bpt_graph_transposed_to_host", "bpt_graph_destroy", "bpt_attn_fwd_workspace", "bpt_attn_bwd_workspace",
     "bpt_attn_fwd", "bpt_attn_bwd", "bpt_attn_bwd_query_side", "bpt_attn_bwd_key_side", "bpt_profile_enable",
     "bpt_profile_report", "bpt_layer_fwd_workspace", "bpt_layer_fwd", "bpt_layer_bwd_workspace", "bpt_layer_bwd",
+    "bpt_stack_fwd_workspace", "bpt_stack_fwd", "bpt_stack_bwd_workspace", "bpt_stack_bwd",
     "bpt_count_edges", "bpt_strerror",
 ]
 
@@ -106,6 +107,15 @@ def load_library() -> ctypes.CDLL:
     L.bpt_layer_bwd_workspace.argtypes = [vp, i32, i32, i32]
     L.bpt_layer_bwd.restype = ctypes.c_int
     L.bpt_layer_bwd.argtypes = [vp, i32, i32, ctypes.c_float, vp, vp, vp, P(BptLayerParams), vp, sz, vp, vp, vp,
+                                P(BptLayerGrads), vp, sz, vp]
+    L.bpt_stack_fwd_workspace.restype = sz
+    L.bpt_stack_fwd_workspace.argtypes = [vp, i32, i32, i32, i32]
+    L.bpt_stack_fwd.restype = ctypes.c_int
+    L.bpt_stack_fwd.argtypes = [vp, i32, i32, i32, ctypes.c_float, vp, P(vp), vp, P(BptLayerParams), vp, vp, vp, sz, vp]
+    L.bpt_stack_bwd_workspace.restype = sz
+    L.bpt_stack_bwd_workspace.argtypes = [vp, i32, i32, i32]
+    L.bpt_stack_bwd.restype = ctypes.c_int
+    L.bpt_stack_bwd.argtypes = [vp, i32, i32, i32, ctypes.c_float, vp, P(vp), P(BptLayerParams), vp, sz, vp, vp, vp, P(vp),
                                 P(BptLayerGrads), vp, sz, vp]
     L.bpt_count_edges.restype = ctypes.c_int
     L.bpt_count_edges.argtypes = [i32, i32, i32, i32, P(i64)]
@@ -323,12 +333,11 @@ def bpt_attn_bwd_key_side(g: Graph, Q, K, V, rel, lse, dout, dK, dV, workspace, 
     return dK, dV
 
 
-def _layer_args(g: Graph, X: torch.Tensor, rel: torch.Tensor, params: dict, heads: int, eps: float,
-                seq_len: Optional[torch.Tensor]):
-    """Checks the tensors of a layer call; returns (d_ff, the parameter struct, the seq_len pointer)."""
+def _layer_params(g: Graph, B: int, device, rel: torch.Tensor, params: dict, heads: int, eps: float,
+                  seq_len: Optional[torch.Tensor]):
+    """Checks the table, the parameters and the lengths of a layer call on B batch entries; returns (d_ff, the
+    parameter struct, the seq_len pointer)."""
     d = heads * 64
-    if X.dtype != torch.bfloat16 or X.dim() != 3 or X.shape[1] != g.num_nodes or X.shape[2] != d or not X.is_contiguous():
-        raise ValueError("X must be a contiguous bf16 [B, %d, %d] tensor" % (g.num_nodes, d))
     if rel.dtype != torch.bfloat16 or tuple(rel.shape) != (g.num_levels, g.rel_width, 64) or not rel.is_contiguous():
         raise ValueError("rel must be contiguous bf16 [%d,%d,64]" % (g.num_levels, g.rel_width))
     d_ff = params["W1"].shape[1]
@@ -337,16 +346,26 @@ def _layer_args(g: Graph, X: torch.Tensor, rel: torch.Tensor, params: dict, head
     for name, shape in want.items():
         t = params[name]
         dt = torch.bfloat16 if name.startswith("W") else torch.float32
-        if t.dtype != dt or tuple(t.shape) != shape or not t.is_contiguous() or t.device != X.device:
-            raise ValueError("parameter %s must be a contiguous %s tensor of shape %s on the device of X" % (name, dt, shape))
+        if t.dtype != dt or tuple(t.shape) != shape or not t.is_contiguous() or t.device != device:
+            raise ValueError("parameter %s must be a contiguous %s tensor of shape %s on the device of the input"
+                             % (name, dt, shape))
     lens = None
     if seq_len is not None:
-        if seq_len.dtype != torch.int32 or tuple(seq_len.shape) != (X.shape[0],) or not seq_len.is_contiguous():
+        if seq_len.dtype != torch.int32 or tuple(seq_len.shape) != (B,) or not seq_len.is_contiguous():
             raise ValueError("seq_len must be a contiguous int32 tensor of B entries")
         lens = seq_len.data_ptr()
     lp = BptLayerParams(*[params[n].data_ptr() for n in ("Wq", "Wk", "Wv", "Wo", "W1", "W2", "b1", "b2", "g1", "beta1",
                                                           "g2", "beta2")], d_ff, float(eps))
     return d_ff, lp, lens
+
+
+def _layer_args(g: Graph, X: torch.Tensor, rel: torch.Tensor, params: dict, heads: int, eps: float,
+                seq_len: Optional[torch.Tensor]):
+    """Checks the tensors of a layer call; returns (d_ff, the parameter struct, the seq_len pointer)."""
+    d = heads * 64
+    if X.dtype != torch.bfloat16 or X.dim() != 3 or X.shape[1] != g.num_nodes or X.shape[2] != d or not X.is_contiguous():
+        raise ValueError("X must be a contiguous bf16 [B, %d, %d] tensor" % (g.num_nodes, d))
+    return _layer_params(g, X.shape[0], X.device, rel, params, heads, eps, seq_len)
 
 
 def bpt_layer_fwd(g: Graph, X: torch.Tensor, rel: torch.Tensor, params: dict, heads: int, scale: Optional[float] = None,
@@ -406,6 +425,87 @@ def bpt_layer_bwd(g: Graph, X: torch.Tensor, rel: torch.Tensor, params: dict, he
                            d_rel.data_ptr(), ctypes.byref(lg), workspace.data_ptr(), workspace.numel(), _stream_ptr()),
            "bpt_layer_bwd")
     return dX, d_rel, grads
+
+
+def _stack_args(g: Graph, E: torch.Tensor, rels, params, heads: int, eps: float, seq_len: Optional[torch.Tensor]):
+    """Checks the tensors of a stack call; returns (d_ff, array of parameter structs, array of rel pointers, the
+    seq_len pointer)."""
+    d = heads * 64
+    if E.dtype != torch.bfloat16 or E.dim() != 3 or E.shape[1] != g.n or E.shape[2] != d or not E.is_contiguous():
+        raise ValueError("E must be a contiguous bf16 [B, %d, %d] tensor" % (g.n, d))
+    if len(params) < 1 or len(rels) != len(params):
+        raise ValueError("one parameter dict and one rel table per layer")
+    structs, lens, d_ff = [], None, None
+    for rel, p in zip(rels, params):
+        f, lp, lens = _layer_params(g, E.shape[0], E.device, rel, p, heads, eps, seq_len)
+        if d_ff is not None and f != d_ff:
+            raise ValueError("every layer must have the same d_ff")
+        d_ff = f
+        structs.append(lp)
+    return (d_ff, (BptLayerParams * len(params))(*structs),
+            (ctypes.c_void_p * len(rels))(*[r.data_ptr() for r in rels]), lens)
+
+
+def stack_workspace_bytes(g: Graph, B: int, heads: int, d_ff: int, num_layers: int) -> Tuple[int, int]:
+    """Bytes of workspace bpt_stack_fwd and bpt_stack_bwd need."""
+    L = load_library()
+    return (int(L.bpt_stack_fwd_workspace(g.handle, B, heads, d_ff, num_layers)),
+            int(L.bpt_stack_bwd_workspace(g.handle, B, heads, d_ff)))
+
+
+def bpt_stack_fwd(g: Graph, E: torch.Tensor, rels, params, heads: int, scale: Optional[float] = None, eps: float = 1e-5,
+                  seq_len: Optional[torch.Tensor] = None, want_root: bool = True, want_tokens: bool = True,
+                  workspace: Optional[torch.Tensor] = None):
+    """The update of the graph (Sec. 3.3) over len(params) layers: E [B, n, heads*64] bf16 token embeddings ->
+    (root [B, d] or None, tokens [B, n, d] or None).  rels: one [levels, rel_width, 64] bf16 table per layer;
+    params: one dict per layer as for bpt_layer_fwd.  Pass a `workspace` (stack_workspace_bytes) to keep the
+    activations for bpt_stack_bwd."""
+    L = load_library()
+    d_ff, lps, relp, lens = _stack_args(g, E, rels, params, heads, eps, seq_len)
+    if not (want_root or want_tokens):
+        raise ValueError("ask for the root, the tokens or both")
+    B, d = E.shape[0], heads * 64
+    root = torch.empty((B, d), dtype=E.dtype, device=E.device) if want_root else None
+    tokens = torch.empty_like(E) if want_tokens else None
+    need = int(L.bpt_stack_fwd_workspace(g.handle, B, heads, d_ff, len(params)))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=E.device)
+    _check(L.bpt_stack_fwd(g.handle, B, heads, len(params), float(scale) if scale else 0.0, lens, relp, E.data_ptr(), lps,
+                           root.data_ptr() if want_root else None, tokens.data_ptr() if want_tokens else None,
+                           workspace.data_ptr(), workspace.numel(), _stream_ptr()), "bpt_stack_fwd")
+    return root, tokens
+
+
+def bpt_stack_bwd(g: Graph, E: torch.Tensor, rels, params, heads: int, fwd_workspace: torch.Tensor,
+                  d_root: Optional[torch.Tensor], d_tokens: Optional[torch.Tensor], scale: Optional[float] = None,
+                  eps: float = 1e-5, seq_len: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None):
+    """Backward of bpt_stack_fwd, called with the same arguments and the workspace that call filled.  d_root [B, d]
+    and / or d_tokens [B, n, d] in bf16.  Returns (dE bf16 like E, list of d_rel fp32 per layer, list of dicts of
+    fp32 parameter gradients per layer)."""
+    L = load_library()
+    d_ff, lps, relp, lens = _stack_args(g, E, rels, params, heads, eps, seq_len)
+    B, d = E.shape[0], heads * 64
+    for name, t, shape in (("d_root", d_root, (B, d)), ("d_tokens", d_tokens, tuple(E.shape))):
+        if t is not None and (t.dtype != torch.bfloat16 or tuple(t.shape) != shape or not t.is_contiguous()
+                              or t.device != E.device):
+            raise ValueError("%s must be a contiguous bf16 tensor of shape %s on the device of E" % (name, shape))
+    if d_root is None and d_tokens is None:
+        raise ValueError("pass d_root, d_tokens or both")
+    dE = torch.empty_like(E)
+    d_rels = [torch.empty(r.shape, dtype=torch.float32, device=E.device) for r in rels]
+    grads = [{"d" + n: torch.empty(p[n].shape, dtype=torch.float32, device=E.device) for n in
+              ("Wq", "Wk", "Wv", "Wo", "W1", "b1", "W2", "b2", "g1", "beta1", "g2", "beta2")} for p in params]
+    lgs = (BptLayerGrads * len(params))(*[BptLayerGrads(*[gr[n].data_ptr() for n in GRAD_NAMES]) for gr in grads])
+    drp = (ctypes.c_void_p * len(rels))(*[t.data_ptr() for t in d_rels])
+    need = int(L.bpt_stack_bwd_workspace(g.handle, B, heads, d_ff))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=E.device)
+    _check(L.bpt_stack_bwd(g.handle, B, heads, len(params), float(scale) if scale else 0.0, lens, relp, lps,
+                           fwd_workspace.data_ptr(), fwd_workspace.numel(),
+                           d_root.data_ptr() if d_root is not None else None,
+                           d_tokens.data_ptr() if d_tokens is not None else None, dE.data_ptr(), drp, lgs,
+                           workspace.data_ptr(), workspace.numel(), _stream_ptr()), "bpt_stack_bwd")
+    return dE, d_rels, grads
 
 
 class GraphAttentionFunction(torch.autograd.Function):

@@ -1,6 +1,8 @@
 // The graph layer around graph self-attention (Sec. 3.1 and Sec. 3.3, the update of the graph):
 //   Z = norm(X + [head_1 .. head_H] Wo),   Y = norm(Z + max(0, Z W1 + b1) W2 + b2)
-// for all 2n-1 nodes, forward and backward.  The dense maps are plain library GEMMs (rocBLAS,
+// for all 2n-1 nodes, forward and backward, and the loop over layers from the initial states
+// (embeddings on the token rows, zero on the span rows) to the root or token rows of the last
+// layer.  The dense maps are plain library GEMMs (rocBLAS,
 // bf16 operands, fp32 accumulation); attention is this library's own forward and backward on the
 // [B][N][H][64] layout the projections produce (no transposes); residual + bias + layer
 // normalisation, bias + ReLU, their backward counterparts and the fixed-order column sums are
@@ -358,6 +360,50 @@ __global__ void __launch_bounds__(256) add_cast_kernel(const bf16_t* __restrict_
     *reinterpret_cast<uint4*>(y + i * 8) = make_uint4(o[0], o[1], o[2], o[3]);
 }
 
+// Sec. 3.3, the states before the first layer: token nodes start from their embeddings, span nodes from
+// zero.  e: [B][n][d], h: [B][N][d], 8 values per thread.
+__global__ void __launch_bounds__(256) initial_states_kernel(const bf16_t* __restrict__ e, bf16_t* __restrict__ h, int64_t chunks,
+                                                             int n, int N, int row_chunks) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= chunks) return;
+    const int64_t row = i / row_chunks;
+    const int c = (int)(i - row * row_chunks), v = (int)(row % N);
+    const int64_t b = row / N;
+    uint4 x = make_uint4(0u, 0u, 0u, 0u);
+    if (v < n) x = *reinterpret_cast<const uint4*>(e + ((b * n + v) * row_chunks + c) * 8);
+    *reinterpret_cast<uint4*>(h + i * 8) = x;
+}
+
+// Sec. 3.3, the output: the root's row and / or the token rows of h [B][N][d], to root [B][d] and tokens
+// [B][n][d] (either may be null).  One thread per 8 values of the rows that are read.
+__global__ void __launch_bounds__(256) readout_kernel(const bf16_t* __restrict__ h, bf16_t* __restrict__ root,
+                                                      bf16_t* __restrict__ tokens, int64_t chunks, int n, int N, int row_chunks) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= chunks) return;
+    const int64_t row = i / row_chunks;   // over [B][n + 1]: the tokens, then the root
+    const int c = (int)(i - row * row_chunks), v = (int)(row % (n + 1));
+    const int64_t b = row / (n + 1);
+    bf16_t* dst = v < n ? tokens : root;
+    if (!dst) return;
+    const uint4 x = *reinterpret_cast<const uint4*>(h + ((b * N + (v < n ? v : N - 1)) * row_chunks + c) * 8);
+    *reinterpret_cast<uint4*>(dst + ((v < n ? b * n + v : b) * row_chunks + c) * 8) = x;
+}
+
+// the reverse: the gradient with respect to the last states is d_tokens on the token rows, d_root on the
+// root's row (a null one counts as zero) and zero on every other row
+__global__ void __launch_bounds__(256) readout_bwd_kernel(const bf16_t* __restrict__ d_root, const bf16_t* __restrict__ d_tokens,
+                                                          bf16_t* __restrict__ dh, int64_t chunks, int n, int N, int row_chunks) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= chunks) return;
+    const int64_t row = i / row_chunks;
+    const int c = (int)(i - row * row_chunks), v = (int)(row % N);
+    const int64_t b = row / N;
+    uint4 x = make_uint4(0u, 0u, 0u, 0u);
+    if (v < n && d_tokens) x = *reinterpret_cast<const uint4*>(d_tokens + ((b * n + v) * row_chunks + c) * 8);
+    if (v == N - 1 && d_root) x = *reinterpret_cast<const uint4*>(d_root + (b * row_chunks + c) * 8);
+    *reinterpret_cast<uint4*>(dh + i * 8) = x;
+}
+
 // one rocBLAS handle per host thread and device, created on first use and kept: a handle carries the
 // stream of the call in progress, so two host threads must not share one
 rocblas_handle blas_handle(int device) {
@@ -532,6 +578,21 @@ int gemm_at_b_sliced(rocblas_handle h, int M, int N, int64_t K, const void* A, c
     return BPT_OK;
 }
 
+// Workspace of the stack's forward: the states H^0 .. H^layers, then one layer workspace per layer.
+struct StackBuffers {
+    size_t state_bytes, layer_bytes, layers_at, total;
+};
+StackBuffers stack_buffers(const bpt_graph* g, int B, int H, int d_ff, int num_layers) {
+    const bpt_shape_t s = attn_shape(g, B, H, 0.f, nullptr);
+    StackBuffers S;
+    S.state_bytes = align_up((size_t)B * g->num_nodes * H * kD * 2);
+    S.layer_bytes = align_up(layer_buffers(g, B, H, d_ff, bpt_attn_fwd_workspace(g, &s)).total);
+    S.layers_at = S.state_bytes * ((size_t)num_layers + 1);
+    S.total = S.layers_at + S.layer_bytes * (size_t)num_layers;
+    return S;
+}
+constexpr int kMaxStackLayers = 256;
+
 }  // namespace
 }  // namespace bpt
 
@@ -684,6 +745,98 @@ int bpt_layer_bwd(const bpt_graph_t* g, int32_t B, int32_t H, float scale, const
         return rc;
     BPT_LAUNCH("add_cast_kernel", add_cast_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st,
                static_cast<const bf16_t*>(ds1), static_cast<const float*>(t), static_cast<bf16_t*>(dX), chunks);
+    BPT_HIP(hipGetLastError());
+    return BPT_OK;
+}
+
+size_t bpt_stack_fwd_workspace(const bpt_graph_t* g, int32_t B, int32_t H, int32_t d_ff, int32_t num_layers) {
+    if (!g || B < 1 || H < 1 || d_ff < 8 || num_layers < 1 || num_layers > kMaxStackLayers) return 0;
+    return stack_buffers(g, B, H, d_ff, num_layers).total;
+}
+
+int bpt_stack_fwd(const bpt_graph_t* g, int32_t B, int32_t H, int32_t num_layers, float scale, const int32_t* seq_len,
+                  const void* const* rel, const void* E, const bpt_layer_params_t* p, void* root, void* tokens, void* workspace,
+                  size_t workspace_bytes, void* stream) {
+    if (!g || !rel || !E || !p || (!root && !tokens) || !workspace || B < 1 || H < 1 || num_layers < 1)
+        return BPT_ERR_INVALID_ARG;
+    if (num_layers > kMaxStackLayers) return BPT_ERR_UNSUPPORTED;
+    for (int l = 0; l < num_layers; ++l) {
+        if (!rel[l]) return BPT_ERR_INVALID_ARG;
+        if (p[l].d_ff != p[0].d_ff) return BPT_ERR_UNSUPPORTED;   // one workspace size serves every layer
+    }
+    if (p[0].d_ff < 8) return BPT_ERR_UNSUPPORTED;
+    const StackBuffers S = stack_buffers(g, B, H, p[0].d_ff, num_layers);
+    if (S.total > workspace_bytes) return BPT_ERR_INVALID_ARG;
+    const int64_t rows = (int64_t)B * g->num_nodes;
+    if (rows > INT32_MAX) return BPT_ERR_UNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    const int row_chunks = H * kD / 8;
+    const int64_t chunks = rows * row_chunks;
+    BPT_LAUNCH("initial_states_kernel", initial_states_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st,
+               static_cast<const bf16_t*>(E), reinterpret_cast<bf16_t*>(ws), chunks, g->n, g->num_nodes, row_chunks);
+    BPT_HIP(hipGetLastError());
+    for (int l = 0; l < num_layers; ++l) {
+        const int rc = bpt_layer_fwd(g, B, H, scale, seq_len, rel[l], ws + S.state_bytes * l, &p[l], ws + S.state_bytes * (l + 1),
+                                     ws + S.layers_at + S.layer_bytes * l, S.layer_bytes, stream);
+        if (rc) return rc;
+    }
+    const int64_t out_chunks = (int64_t)B * (g->n + 1) * row_chunks;
+    BPT_LAUNCH("readout_kernel", readout_kernel, dim3((unsigned)((out_chunks + 255) / 256)), dim3(256), 0, st,
+               reinterpret_cast<const bf16_t*>(ws + S.state_bytes * num_layers), static_cast<bf16_t*>(root),
+               static_cast<bf16_t*>(tokens), out_chunks, g->n, g->num_nodes, row_chunks);
+    BPT_HIP(hipGetLastError());
+    return BPT_OK;
+}
+
+size_t bpt_stack_bwd_workspace(const bpt_graph_t* g, int32_t B, int32_t H, int32_t d_ff) {
+    if (!g || B < 1 || H < 1 || d_ff < 8) return 0;
+    const size_t layer = bpt_layer_bwd_workspace(g, B, H, d_ff);
+    return layer ? 2 * align_up((size_t)B * g->num_nodes * H * kD * 2) + layer : 0;
+}
+
+int bpt_stack_bwd(const bpt_graph_t* g, int32_t B, int32_t H, int32_t num_layers, float scale, const int32_t* seq_len,
+                  const void* const* rel, const bpt_layer_params_t* p, const void* fwd_workspace, size_t fwd_workspace_bytes,
+                  const void* d_root, const void* d_tokens, void* dE, float* const* d_rel, const bpt_layer_grads_t* grads,
+                  void* workspace, size_t workspace_bytes, void* stream) {
+    if (!g || !rel || !p || !fwd_workspace || (!d_root && !d_tokens) || !dE || !d_rel || !grads || !workspace || B < 1 ||
+        H < 1 || num_layers < 1)
+        return BPT_ERR_INVALID_ARG;
+    if (num_layers > kMaxStackLayers) return BPT_ERR_UNSUPPORTED;
+    for (int l = 0; l < num_layers; ++l) {
+        if (!rel[l] || !d_rel[l]) return BPT_ERR_INVALID_ARG;
+        if (p[l].d_ff != p[0].d_ff) return BPT_ERR_UNSUPPORTED;
+    }
+    if (p[0].d_ff < 8) return BPT_ERR_UNSUPPORTED;
+    const StackBuffers S = stack_buffers(g, B, H, p[0].d_ff, num_layers);
+    if (S.total > fwd_workspace_bytes) return BPT_ERR_INVALID_ARG;
+    const size_t need = bpt_stack_bwd_workspace(g, B, H, p[0].d_ff);
+    if (!need || need > workspace_bytes) return BPT_ERR_INVALID_ARG;
+    const int64_t rows = (int64_t)B * g->num_nodes;
+    if (rows > INT32_MAX) return BPT_ERR_UNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const unsigned char* fw = static_cast<const unsigned char*>(fwd_workspace);
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    unsigned char* dh[2] = {ws, ws + S.state_bytes};   // gradients with respect to the states, alternating
+    unsigned char* layer_ws = ws + 2 * S.state_bytes;
+    const int row_chunks = H * kD / 8;
+    const int64_t chunks = rows * row_chunks;
+    BPT_LAUNCH("readout_bwd_kernel", readout_bwd_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st,
+               static_cast<const bf16_t*>(d_root), static_cast<const bf16_t*>(d_tokens), reinterpret_cast<bf16_t*>(dh[0]), chunks,
+               g->n, g->num_nodes, row_chunks);
+    BPT_HIP(hipGetLastError());
+    int cur = 0;
+    for (int l = num_layers - 1; l >= 0; --l, cur ^= 1) {
+        const int rc = bpt_layer_bwd(g, B, H, scale, seq_len, rel[l], fw + S.state_bytes * l, &p[l],
+                                     fw + S.layers_at + S.layer_bytes * l, S.layer_bytes, dh[cur], dh[cur ^ 1], d_rel[l], &grads[l],
+                                     layer_ws, workspace_bytes - 2 * S.state_bytes, stream);
+        if (rc) return rc;
+    }
+    // the embeddings are the token rows of the first states; the zero rows of the spans have no parameter behind them
+    const int64_t out_chunks = (int64_t)B * (g->n + 1) * row_chunks;
+    BPT_LAUNCH("readout_kernel", readout_kernel, dim3((unsigned)((out_chunks + 255) / 256)), dim3(256), 0, st,
+               reinterpret_cast<const bf16_t*>(dh[cur]), static_cast<bf16_t*>(nullptr), static_cast<bf16_t*>(dE), out_chunks, g->n,
+               g->num_nodes, row_chunks);
     BPT_HIP(hipGetLastError());
     return BPT_OK;
 }

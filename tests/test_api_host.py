@@ -70,6 +70,9 @@ def test_null_graph_is_an_error_everywhere():
     assert lib.bpt_layer_fwd_workspace(None, 1, 1, 64) == 0 and lib.bpt_layer_bwd_workspace(None, 1, 1, 64) == 0
     assert lib.bpt_layer_fwd(None, 1, 1, 0.0, *([None] * 6), 0, None) == bpt.BPT_ERR_INVALID_ARG
     assert lib.bpt_layer_bwd(None, 1, 1, 0.0, *([None] * 5), 0, *([None] * 5), 0, None) == bpt.BPT_ERR_INVALID_ARG
+    assert lib.bpt_stack_fwd_workspace(None, 1, 1, 64, 2) == 0 and lib.bpt_stack_bwd_workspace(None, 1, 1, 64) == 0
+    assert lib.bpt_stack_fwd(None, 1, 1, 2, 0.0, *([None] * 7), 0, None) == bpt.BPT_ERR_INVALID_ARG
+    assert lib.bpt_stack_bwd(None, 1, 1, 2, 0.0, *([None] * 4), 0, *([None] * 6), 0, None) == bpt.BPT_ERR_INVALID_ARG
     lib.bpt_graph_destroy(None)                  # a no-op, must not crash
 
 

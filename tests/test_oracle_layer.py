@@ -1,6 +1,7 @@
 """Pins for the oracle of the graph layer (CPU only): library routines of torch for the dense parts
 (linear maps, layer normalisation, ReLU), the already pinned attention oracle in between."""
 import numpy as np
+import pytest
 import torch
 
 import oracle
@@ -216,3 +217,97 @@ def test_layer_backward_for_k_at_least_n_is_the_transformer_encoder_layer():
     assert close(got["dW2"], enc.linear2.weight.grad.numpy().T) and close(got["db2"], enc.linear2.bias.grad.numpy())
     assert close(got["dg1"], enc.norm1.weight.grad.numpy()) and close(got["dbeta1"], enc.norm1.bias.grad.numpy())
     assert close(got["dg2"], enc.norm2.weight.grad.numpy()) and close(got["dbeta2"], enc.norm2.bias.grad.numpy())
+
+
+# ------------------------------------------------------------------ the stack of layers (Sec. 3.3, the whole loop)
+from oracle.layer import stack_backward, stack_forward   # noqa: E402
+
+
+def encoder_like(p, d, heads, d_ff):
+    """torch's post-norm encoder layer carrying the parameters p (float64)."""
+    enc = torch.nn.TransformerEncoderLayer(d, heads, d_ff, dropout=0.0, activation="relu", batch_first=True,
+                                           norm_first=False, dtype=torch.float64)
+    t = lambda a: torch.tensor(np.asarray(a, dtype=np.float64))
+    with torch.no_grad():
+        enc.self_attn.in_proj_weight.copy_(torch.cat([t(p["Wq"]).T, t(p["Wk"]).T, t(p["Wv"]).T]))
+        enc.self_attn.in_proj_bias.zero_()
+        enc.self_attn.out_proj.weight.copy_(t(p["Wo"]).T)
+        enc.self_attn.out_proj.bias.zero_()
+        for mod, w, b in ((enc.linear1, "W1", "b1"), (enc.linear2, "W2", "b2")):
+            mod.weight.copy_(t(p[w]).T)
+            mod.bias.copy_(t(p[b]))
+        for mod, w, b in ((enc.norm1, "g1", "beta1"), (enc.norm2, "g2", "beta2")):
+            mod.weight.copy_(t(p[w]))
+            mod.bias.copy_(t(p[b]))
+    return enc
+
+
+def test_stack_for_k_at_least_n_is_a_stack_of_transformer_encoder_layers():
+    # Sec. 3.3: with every token attending to all tokens the token rows are the vanilla Transformer's, layer
+    # after layer (the span rows change from layer to layer but no token reads them); forward and backward
+    n, heads, d_ff, layers = 16, 2, 128, 3
+    d = heads * 64
+    rng = np.random.default_rng(21)
+    g = oracle.build_graph(n, n, False)
+    E = rng.standard_normal((2, n, d)).astype(np.float32)
+    d_tokens = rng.standard_normal((2, n, d)).astype(np.float32)
+    Rels = [np.zeros((g.num_levels, g.rel_width, 64), dtype=np.float32)] * layers
+    params = [make_params(rng, d, d_ff) for _ in range(layers)]
+    root, tokens, states = stack_forward(n, n, False, heads, E, Rels, params, 0.125)
+    assert len(states) == layers + 1 and np.abs(states[0][:, n:]).max() == 0 and np.array_equal(states[0][:, :n], E)
+    encs = [encoder_like(p, d, heads, d_ff) for p in params]
+    Et = torch.tensor(E.astype(np.float64), requires_grad=True)
+    x = Et
+    for enc in encs:
+        x = enc(x)
+    assert np.abs(tokens - x.detach().numpy()).max() < 1e-5
+    x.backward(torch.tensor(d_tokens.astype(np.float64)))
+    dE, grads = stack_backward(n, n, False, heads, E, Rels, params, np.zeros((2, d)), d_tokens, 0.125)
+    close = lambda a, r: np.abs(a - r).max() <= 5e-5 * max(1.0, float(np.abs(r).max()))
+    assert close(dE, Et.grad.numpy())
+    for gr, enc in zip(grads, encs):   # every layer's own parameters, first layer first
+        wq, wk, wv = (w.numpy().T for w in enc.self_attn.in_proj_weight.grad.split(d))
+        assert close(gr["dWq"], wq) and close(gr["dWk"], wk) and close(gr["dWv"], wv)
+        assert close(gr["dWo"], enc.self_attn.out_proj.weight.grad.numpy().T)
+        assert close(gr["dW1"], enc.linear1.weight.grad.numpy().T) and close(gr["db1"], enc.linear1.bias.grad.numpy())
+        assert close(gr["dW2"], enc.linear2.weight.grad.numpy().T) and close(gr["db2"], enc.linear2.bias.grad.numpy())
+        assert close(gr["dg1"], enc.norm1.weight.grad.numpy()) and close(gr["dbeta1"], enc.norm1.bias.grad.numpy())
+        assert close(gr["dg2"], enc.norm2.weight.grad.numpy()) and close(gr["dbeta2"], enc.norm2.bias.grad.numpy())
+
+
+@pytest.mark.parametrize("n,k,causal,lengths", [(16, 2, False, None), (16, 1, True, None), (16, 2, False, [16, 7])])
+def test_stack_backward_equals_autograd_through_dense_compositions(n, k, causal, lengths):
+    # root and token outputs, span rows carried from layer to layer: autograd through the dense composition of
+    # every layer (the library routines of torch), from the zero-initialised span rows to both outputs
+    heads, d_ff, B, layers = 1, 96, 2, 2
+    d = heads * 64
+    rng = np.random.default_rng(31 + n + k)
+    g = oracle.build_graph(n, k, causal)
+    N = g.num_nodes
+    E = rng.standard_normal((B, n, d)).astype(np.float32)
+    d_root = rng.standard_normal((B, d)).astype(np.float32)
+    d_tokens = rng.standard_normal((B, n, d)).astype(np.float32)
+    Rels = [(0.3 * rng.standard_normal((g.num_levels, g.rel_width, 64))).astype(np.float32) for _ in range(layers)]
+    params = [make_params(rng, d, d_ff) for _ in range(layers)]
+    root, tokens, _ = stack_forward(n, k, causal, heads, E, Rels, params, 0.125, lengths=lengths)
+    dE, grads = stack_backward(n, k, causal, heads, E, Rels, params, d_root, d_tokens, 0.125, lengths=lengths)
+
+    graphs = [g] * B if lengths is None else [oracle.build_graph_len(n, L, k, causal) for L in lengths]
+    masks, ids = dense_graph_tables(graphs, N)
+    t = lambda a: torch.tensor(np.asarray(a, dtype=np.float64), requires_grad=True)
+    Et, Rt, Pt = t(E), [t(r) for r in Rels], [{w: t(p[w]) for w in PARAMS} for p in params]
+    x = torch.cat([Et, torch.zeros((B, N - n, d), dtype=torch.float64)], 1)
+    for R, P in zip(Rt, Pt):
+        x = torch_layer(x, R, P, masks, ids, heads, 0.125)
+    keep = torch.tensor(kept_rows(n, lengths if lengths is not None else [n] * B))
+    assert np.abs(root - x[:, N - 1].detach().numpy()).max() < 1e-5
+    assert np.abs((tokens - x[:, :n].detach().numpy())[keep[:, :n].numpy()]).max() < 1e-5
+    loss = (x[:, N - 1] * torch.tensor(d_root.astype(np.float64))).sum() + \
+           (x[:, :n] * torch.tensor(d_tokens.astype(np.float64)) * keep[:, :n, None]).sum()
+    loss.backward()
+    close = lambda a, r: np.abs(a - r).max() <= 5e-5 * max(1.0, float(np.abs(r).max()))
+    assert close(dE, Et.grad.numpy())
+    for gr, R, P in zip(grads, Rt, Pt):
+        assert close(gr["dRel"], R.grad.numpy())
+        for w in PARAMS:
+            assert close(gr["d" + w], P[w].grad.numpy()), w
