@@ -296,5 +296,23 @@ struct TileWalk {
     }
 };
 
+// Stores of results that no kernel of this library reads again (out, dQ, dK, dV): marked non-temporal, so
+// that the lines do not push the rows the gathers share out of L2 (lm: forward + backward 0.588 -> 0.564 ms).
+template <typename T>
+__device__ __forceinline__ void store_once(T* p, T v) {
+    __builtin_nontemporal_store(v, p);
+}
+// 16 bytes of a row that a kernel reads once (the backward's own Q, dO and K, V tiles, as opposed to the rows
+// it gathers): non-temporal as well (-1 % on the two backward kernels; the forward's Q tile is better off plain)
+template <typename V>
+__device__ __forceinline__ V load_once16(const void* p) {
+    typedef uint32_t vec4 __attribute__((ext_vector_type(4)));
+    return __builtin_bit_cast(V, __builtin_nontemporal_load(reinterpret_cast<const vec4*>(p)));
+}
+__device__ __forceinline__ void store_once(float4* p, float4 v) {
+    typedef float vec4 __attribute__((ext_vector_type(4)));
+    __builtin_nontemporal_store(vec4{v.x, v.y, v.z, v.w}, reinterpret_cast<vec4*>(p));
+}
+
 }  // namespace
 }  // namespace bpt

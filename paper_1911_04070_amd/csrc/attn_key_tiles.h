@@ -152,10 +152,10 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyA
 
         // B operands: the tile's keys (lane j <-> key j) and the rows of the table this level can meet
         const int64_t krow = base + (int64_t)(node0 + min(j, nkeys - 1)) * a.sn + 16 * g;
-        const bf16x8_t kb0 = *reinterpret_cast<const bf16x8_t*>(a.K + krow);
-        const bf16x8_t kb1 = *reinterpret_cast<const bf16x8_t*>(a.K + krow + 8);
-        const bf16x8_t vb0 = *reinterpret_cast<const bf16x8_t*>(a.V + krow);
-        const bf16x8_t vb1 = *reinterpret_cast<const bf16x8_t*>(a.V + krow + 8);
+        const bf16x8_t kb0 = load_once16<bf16x8_t>(a.K + krow);
+        const bf16x8_t kb1 = load_once16<bf16x8_t>(a.K + krow + 8);
+        const bf16x8_t vb0 = load_once16<bf16x8_t>(a.V + krow);
+        const bf16x8_t vb1 = load_once16<bf16x8_t>(a.V + krow + 8);
         constexpr int kInRegs = NBC < kRegBiasChunks ? NBC : kRegBiasChunks;
         bf16x8_t rb[kInRegs][2];
 #pragma unroll
@@ -322,7 +322,10 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyA
                     dst = (q4 < kD ? a.dK + q4 : a.dV + (q4 - kD)) + base + (int64_t)(node0 + key) * a.sn;
                 else
                     dst = a.part + (((int64_t)bh * a.num_part + part) * 16 + key) * (2 * kD) + q4;
-                *reinterpret_cast<float4*>(dst) = v;
+                if (part < 0)
+                    store_once(reinterpret_cast<float4*>(dst), v);
+                else   // the merge kernel reads the partial sums
+                    *reinterpret_cast<float4*>(dst) = v;
             }
         }
         wave_lds_sync();
@@ -361,7 +364,7 @@ __global__ void __launch_bounds__(256) kv_tile_merge_kernel(const KeyArgs a, con
             const int r = lane < 32 ? ra : rb;
             if (r >= 0) {
                 float* dst = ((lane & 16) ? a.dV : a.dK) + base + (int64_t)(first + r) * a.sn + 4 * (lane & 15);
-                *reinterpret_cast<float4*>(dst) = make_float4(0.f, 0.f, 0.f, 0.f);
+                store_once(reinterpret_cast<float4*>(dst), make_float4(0.f, 0.f, 0.f, 0.f));
             }
         }
         return;
@@ -398,7 +401,7 @@ __global__ void __launch_bounds__(256) kv_tile_merge_kernel(const KeyArgs a, con
         const float4 t = make_float4((s0.x + s1.x) + (s2.x + s3.x), (s0.y + s1.y) + (s2.y + s3.y),
                                      (s0.z + s1.z) + (s2.z + s3.z), (s0.w + s1.w) + (s2.w + s3.w));
         float* dst = (q4 < kD ? a.dK + q4 : a.dV + (q4 - kD)) + base + (int64_t)(node0 + key) * a.sn;
-        *reinterpret_cast<float4*>(dst) = t;
+        store_once(reinterpret_cast<float4*>(dst), t);
     }
 }
 

@@ -216,7 +216,7 @@ __global__ void __launch_bounds__(kTileThreads) fwd_span_tile_kernel(const SpanA
                 bf16_t* orow = a.out + base + (int64_t)span_slot_node(grp, slot, a.L, a.n, t0) * a.sn + j;
                 const float inv = lq > 0.f ? 1.f / lq : 0.f;
 #pragma unroll
-                for (int f = 0; f < 4; ++f) orow[16 * f] = (bf16_t)to_bf16_bits(o[f][r] * inv);
+                for (int f = 0; f < 4; ++f) store_once(&orow[16 * f], (bf16_t)to_bf16_bits(o[f][r] * inv));
             }
         } else {
             // partial of the ancestor at level 6 + slot: [bh][level][block][66]
@@ -300,7 +300,7 @@ __device__ __forceinline__ void fwd_span_merge_small(const SpanArgs& a, int item
         acc += o[b] * c;
     }
     const int64_t base = (int64_t)(r.bh / a.H) * a.sb + (int64_t)(r.bh % a.H) * a.sh;
-    a.out[base + (int64_t)r.v * a.sn + lane] = (bf16_t)to_bf16_bits(ls > 0.f ? acc / ls : 0.f);
+    store_once(&a.out[base + (int64_t)r.v * a.sn + lane], (bf16_t)to_bf16_bits(ls > 0.f ? acc / ls : 0.f));
     if (lane == 0) a.lse[(int64_t)r.bh * a.N + r.v] = ls > 0.f ? (mx + fast_log2(ls)) * kLn2 : 0.f;
 }
 
@@ -350,7 +350,7 @@ __global__ void __launch_bounds__(kSpanBigThreads) fwd_span_merge_kernel(const S
             lt += s_l[p];
         }
         const int64_t base = (int64_t)(r.bh / a.H) * a.sb + (int64_t)(r.bh % a.H) * a.sh;
-        a.out[base + (int64_t)r.v * a.sn + t] = (bf16_t)to_bf16_bits(lt > 0.f ? sum / lt : 0.f);
+        store_once(&a.out[base + (int64_t)r.v * a.sn + t], (bf16_t)to_bf16_bits(lt > 0.f ? sum / lt : 0.f));
         if (t == 0) a.lse[(int64_t)r.bh * a.N + r.v] = lt > 0.f ? (mx + fast_log2(lt)) * kLn2 : 0.f;
     }
 }
@@ -474,7 +474,7 @@ __global__ void __launch_bounds__(kTileThreads, 3) bwd_q_span_tile_kernel(const 
                 if (grp == 1 && slot == 15) continue;
                 float* orow = a.dQ + base + (int64_t)span_slot_node(grp, slot, a.L, a.n, t0) * a.sn + j;
 #pragma unroll
-                for (int f = 0; f < 4; ++f) orow[16 * f] = a.scale * dq[f][r];
+                for (int f = 0; f < 4; ++f) store_once(&orow[16 * f], a.scale * dq[f][r]);
             }
         } else {
             uint32_t whi[4], wlo[4], phi[4], plo[4];
@@ -536,7 +536,7 @@ __device__ __forceinline__ void bwd_q_span_merge_small(const SpanArgs& a, int it
             dl += xd[b];
         }
     const int64_t base = (int64_t)(r.bh / a.H) * a.sb + (int64_t)(r.bh % a.H) * a.sh;
-    a.dQ[base + (int64_t)r.v * a.sn + lane] = a.scale * (sa - dl * sb);
+    store_once(&a.dQ[base + (int64_t)r.v * a.sn + lane], a.scale * (sa - dl * sb));
     if (lane == 0) a.stat[(int64_t)r.bh * a.N + r.v] = make_float2(span_row_lse2(a, r), dl);
 }
 
@@ -573,7 +573,7 @@ __global__ void __launch_bounds__(kSpanBigThreads) bwd_q_span_merge_kernel(const
             td += s_d[p];
         }
         const int64_t base = (int64_t)(r.bh / a.H) * a.sb + (int64_t)(r.bh % a.H) * a.sh;
-        a.dQ[base + (int64_t)r.v * a.sn + t] = a.scale * (ta - td * tb);
+        store_once(&a.dQ[base + (int64_t)r.v * a.sn + t], a.scale * (ta - td * tb));
         if (t == 0) a.stat[(int64_t)r.bh * a.N + r.v] = make_float2(span_row_lse2(a, r), td);
     }
 }

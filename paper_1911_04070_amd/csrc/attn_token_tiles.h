@@ -473,7 +473,7 @@ __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArg
                 const float inv = t0 + 4 * g + r < len ? 1.f / __shfl(l, 4 * g + r) : 0.f;
 #pragma unroll
                 for (int f = 0; f < 4; ++f)
-                    orow[(int64_t)(4 * g + r) * a.sn + 16 * f] = (bf16_t)to_bf16_bits(o[f][r] * inv);
+                    store_once(&orow[(int64_t)(4 * g + r) * a.sn + 16 * f], (bf16_t)to_bf16_bits(o[f][r] * inv));
             }
         }
         cc = cr;
@@ -635,10 +635,10 @@ __global__ void __launch_bounds__(kTileThreads, DENSE ? 1 : 2) bwd_q_tile_kernel
             }
         if (c.pair == 0) {   // the tile's own rows: Q^T and dO^T operands (token j, features 16g..16g+15)
             const int64_t at = base + (int64_t)(c.tile * 16 + j) * a.sn + 16 * g;
-            qn0 = *reinterpret_cast<const bf16x8_t*>(a.Q + at);
-            qn1 = *reinterpret_cast<const bf16x8_t*>(a.Q + at + 8);
-            gn0 = *reinterpret_cast<const bf16x8_t*>(a.dout + at);
-            gn1 = *reinterpret_cast<const bf16x8_t*>(a.dout + at + 8);
+            qn0 = load_once16<bf16x8_t>(a.Q + at);
+            qn1 = load_once16<bf16x8_t>(a.Q + at + 8);
+            gn0 = load_once16<bf16x8_t>(a.dout + at);
+            gn1 = load_once16<bf16x8_t>(a.dout + at + 8);
             lse_n = a.lse_r[(int64_t)c.bh * a.N + c.tile * 16 + j];
         }
     };
@@ -897,7 +897,7 @@ __global__ void __launch_bounds__(kTileThreads, DENSE ? 1 : 2) bwd_q_tile_kernel
                 const float dr = __shfl(delta, 4 * g + r);
 #pragma unroll
                 for (int f = 0; f < 4; ++f)
-                    qrow_out[(int64_t)(4 * g + r) * a.sn + 16 * f] = a.scale * (ow[f][r] - dr * op[f][r] + dqr[f][r]);
+                    store_once(&qrow_out[(int64_t)(4 * g + r) * a.sn + 16 * f], a.scale * (ow[f][r] - dr * op[f][r] + dqr[f][r]));
             }
         }
         cc = cr;
