@@ -21,9 +21,11 @@ def say(*a):
     print(*a, flush=True)
 
 
-def tol_for(dtype, ref):
-    """max-abs tolerance of the benchmark spec: 1e-4 for fp32 tensors, 2e-2 for bf16 tensors."""
-    return TOL[dtype]
+def tol_for(dtype, ref, scaled=False):
+    """max-abs tolerance of the benchmark spec: 1e-4 for fp32 tensors, 2e-2 for bf16 tensors.  These are absolute bounds for
+    the task's N(0, 1) inputs, whose results have entries up to about 4; `scaled` (inputs made larger on purpose)
+    lets the bound grow with the largest entry of the expected tensor beyond that."""
+    return TOL[dtype] * (max(1.0, float(np.abs(ref).max()) / 4.0) if scaled else 1.0)
 
 
 def to_dev(x, dtype):
@@ -75,7 +77,7 @@ def test_graph_errors_on_device():
         bpt.bpt_build_graph(48, 2, False)
 
 
-def run_case(w: Workload, x=None, layout="bhnd", check_bwd=None):
+def run_case(w: Workload, x=None, layout="bhnd", check_bwd=None, scaled=False):
     """Runs forward (+ backward) of a workload on the GPU and on the oracle and compares."""
     say("case", w)
     if x is None:
@@ -98,7 +100,7 @@ def run_case(w: Workload, x=None, layout="bhnd", check_bwd=None):
         err = float(np.abs(got - ref).max())
         res[name] = err
         assert np.isfinite(got).all(), name
-        assert err <= tol_for(w.dtype, ref), (name, err)
+        assert err <= tol_for(w.dtype, ref, scaled), (name, err)
     do_bwd = w.backward if check_bwd is None else check_bwd
     if do_bwd:
         grads = bpt.bpt_attn_bwd(g, dev["Q"], dev["K"], dev["V"], rel_d, lse_d, dev["dO"], scale=w.scale)
@@ -110,7 +112,7 @@ def run_case(w: Workload, x=None, layout="bhnd", check_bwd=None):
             res[name] = err
             res[name + "_max"] = float(np.abs(ref).max())
             assert np.isfinite(got).all(), name
-            assert err <= tol_for(w.dtype, ref), (name, err, float(np.abs(ref).max()))
+            assert err <= tol_for(w.dtype, ref, scaled), (name, err, float(np.abs(ref).max()))
         # r_anc never changes the output (it shifts a whole span row): its gradient is zero
         anc = host(grads[3])[1:, w.k + 1]
         assert np.abs(anc).max() <= TOL[w.dtype]
@@ -374,6 +376,25 @@ def test_autograd_function_returns_the_library_gradients():
     for leaf, r in zip(leaves, ref):
         assert torch.equal(leaf.grad, r)
     g.destroy()
+
+
+@pytest.mark.parametrize("dtype,n,k,causal,B,H,q_times,rel_std", [
+    ("bf16", 1024, 4, False, 2, 2, 4.0, 0.5), ("bf16", 1024, 4, True, 2, 2, 8.0, 0.5), ("bf16", 4096, 8, True, 1, 2, 8.0, 0.25),
+    ("f32", 512, 3, False, 1, 2, 4.0, 0.5), ("f32", 512, 3, True, 1, 2, 8.0, 1.0),
+])
+def test_peaked_rows_and_a_large_relative_position_table(dtype, n, k, causal, B, H, q_times, rel_std):
+    # scores with a deviation of 4..8 instead of 1 (most rows put nearly all their weight on one or two keys: lse up
+    # to 48, and dS = w - delta p is a difference of nearly equal numbers) and a table as large as a trained one
+    # (its terms are then a sizeable part of every score, of dQ and of d_rel).  Q is multiplied by a power of
+    # two, which keeps its values exact in bf16; the table is rounded again after scaling.
+    from paper_1911_04070_amd.workloads import REL_STD, round_to_bf16
+    w = Workload("peaked", 9, n, k, causal, B, H, 64, dtype, True)
+    x = make_inputs(w)
+    x["Q"] = (x["Q"] * q_times).astype(np.float32)
+    rel = (x["Rel"] * (rel_std / REL_STD)).astype(np.float32)
+    x["Rel"] = round_to_bf16(rel)[0] if dtype == "bf16" else rel
+    res = run_case(w, x=x, scaled=True)
+    assert res["d_rel_max"] > 10.0   # the table's gradient is not small here
 
 
 def test_scale_argument_and_default():
