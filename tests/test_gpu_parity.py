@@ -397,6 +397,21 @@ def test_peaked_rows_and_a_large_relative_position_table(dtype, n, k, causal, B,
     assert res["d_rel_max"] > 10.0   # the table's gradient is not small here
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_zero_queries_and_zero_values(dtype):
+    # degenerate rows: q = 0 makes every row uniform over its neighbours (lse = ln deg, dK = d_rel = 0);
+    # v = 0 makes out, dP and with them dQ, dK and d_rel exactly zero
+    w = Workload("zeros", 11, 512, 3, False, 2, 2, 64, dtype, True)
+    x = make_inputs(w)
+    x["Q"] = np.zeros_like(x["Q"])
+    res = run_case(w, x=x)
+    assert res["dK_max"] == 0.0 and res["d_rel_max"] == 0.0 and res["dK"] == 0.0 and res["d_rel"] == 0.0
+    x = make_inputs(w)
+    x["V"] = np.zeros_like(x["V"])
+    res = run_case(w, x=x)
+    assert res["out"] == 0.0 and res["dQ"] == 0.0 and res["dK"] == 0.0 and res["d_rel"] == 0.0
+
+
 def test_scale_argument_and_default():
     w = Workload("scale", 10, 256, 2, False, 1, 2, 64, "f32", True)
     x = make_inputs(w)

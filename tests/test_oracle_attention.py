@@ -174,6 +174,34 @@ def test_invariants_constant_values_and_row_shift():
     assert np.all(dRel.reshape(-1, 8)[~used] == 0)
 
 
+@pytest.mark.parametrize("n,k,causal", [(32, 2, False), (64, 3, True)])
+def test_zero_queries_give_uniform_attention_in_closed_form(n, k, causal):
+    # with q_u = 0 every score is 0: lse_u = ln deg(u), out_u = the mean of the neighbours' values, and by the
+    # chain rule dV_v = sum over the rows u that read v of dO_u / deg(u), dS_e = (dO_u . v_e - dO_u . out_u) / deg(u),
+    # dQ_u = scale * sum_e dS_e (k_e + r_e), dK = 0 and d_rel = 0 (both carry a factor q_u)
+    g = oracle.build_graph(n, k, causal)
+    Q, K, V, Rel, dO = rand_inputs(g, 1, 2, 8, seed=12)
+    Q[:] = 0
+    scale = 0.25
+    out, lse, _ = oracle.attn_fwd(g, Q, K, V, Rel, scale)
+    dQ, dK, dV, dRel, _ = oracle.attn_bwd(g, Q, K, V, Rel, dO, scale)
+    deg = np.diff(g.row_ptr)
+    assert np.abs(lse - np.log(deg)[None, None, :]).max() < 1e-13
+    V64, K64, dO64, R64 = (a.astype(np.float64) for a in (V, K, dO, Rel.reshape(-1, Rel.shape[-1])))
+    want_out, want_dV, want_dQ = np.zeros_like(V64), np.zeros_like(V64), np.zeros_like(V64)
+    for u in range(g.num_nodes):
+        e = slice(g.row_ptr[u], g.row_ptr[u + 1])
+        cols = g.col[e]
+        want_out[:, :, u] = V64[:, :, cols].mean(2)
+        np.add.at(want_dV, (slice(None), slice(None), cols), dO64[:, :, u:u + 1] / deg[u])
+        dS = (np.einsum("bhd,bhed->bhe", dO64[:, :, u], V64[:, :, cols])
+              - np.einsum("bhd,bhd->bh", dO64[:, :, u], want_out[:, :, u])[..., None]) / deg[u]
+        want_dQ[:, :, u] = scale * np.einsum("bhe,bhed->bhd", dS, K64[:, :, cols] + R64[g.rel[e]][None, None])
+    assert np.abs(out - want_out).max() < 1e-13
+    assert np.abs(dV - want_dV).max() < 1e-12 and np.abs(dQ - want_dQ).max() < 1e-12
+    assert np.abs(dK).max() == 0 and np.abs(dRel).max() == 0
+
+
 def test_threads_do_not_change_the_result():
     w = shrink(WORKLOADS["cls"], B=2, H=2, n=64)
     g = oracle.build_graph(w.n, w.k, w.causal)
