@@ -238,6 +238,11 @@ __device__ __forceinline__ float2 buf_f2(rsrc_t r, int byte_off) {
     const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(r, byte_off, 0, 0);
     return make_float2(__uint_as_float(v.x), __uint_as_float(v.y));
 }
+// the same for 8 bytes that are read once: the non-temporal bit of the cache policy (aux bit 1)
+__device__ __forceinline__ float2 buf_f2_once(rsrc_t r, int byte_off) {
+    const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(r, byte_off, 0, 2);
+    return make_float2(__uint_as_float(v.x), __uint_as_float(v.y));
+}
 __device__ __forceinline__ void buf_row(rsrc_t r, int byte_off, Row<bf16_t>& out) {
     const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, 0);
     out.w = make_uint4(v.x, v.y, v.z, v.w);

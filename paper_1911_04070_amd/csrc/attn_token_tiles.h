@@ -805,8 +805,8 @@ __global__ void __launch_bounds__(kTileThreads, DENSE ? 1 : 2) bwd_q_tile_kernel
             } else {
                 // (w, p) of this lane's 4 columns: 32 contiguous bytes, a chunk is 2 KB contiguous
                 float4* dst = reinterpret_cast<float4*>(wp_t + ((int64_t)(cc.cp0 + 2 * cc.pair + c) * 16 + j) * 16 + 4 * g);
-                dst[0] = make_float4(pw[c][0], pp[c][0], pw[c][1], pp[c][1]);
-                dst[1] = make_float4(pw[c][2], pp[c][2], pw[c][3], pp[c][3]);
+                store_once(dst, make_float4(pw[c][0], pp[c][0], pw[c][1], pp[c][1]));
+                store_once(dst + 1, make_float4(pw[c][2], pp[c][2], pw[c][3], pp[c][3]));
             }
         }
         // W and P as A operands, each split into bf16 hi + lo: A - delta*Bv cancels when a
@@ -1000,7 +1000,7 @@ __global__ void __launch_bounds__(kThreads, CPW == 2 ? 4 : 2) rel_grad_tile_kern
             const int sl = s_begin + (int)threadIdx.x + k * kThreads;
             const uint32_t off = sl < s_end ? (uint32_t)sl : 0x1FFFFFFFu;   // past the block: an offset outside the buffers
             code[k] = (int)(short)__builtin_amdgcn_raw_buffer_load_b16(rMap, (int)(off * 2u), 0, 0);
-            wpv[k] = buf_f2(rWp, (int)(off * 8u));
+            wpv[k] = buf_f2_once(rWp, (int)(off * 8u));
         }
     };
     // blocks past the end of a shorter sequence add nothing and are stepped over (uniform for the workgroup)
@@ -1069,7 +1069,7 @@ __global__ void __launch_bounds__(kThreads, CPW == 2 ? 4 : 2) rel_grad_tile_kern
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
                 const int row = row0 + 16 * mc + 4 * g + m;
-                if (row < a.n) a.dQ[base + (int64_t)row * a.sn + 16 * fc + j] = dq_old[m] + a.scale * dq[m];
+                if (row < a.n) store_once(&a.dQ[base + (int64_t)row * a.sn + 16 * fc + j], dq_old[m] + a.scale * dq[m]);
             }
         }
         bf16x8_t qb[4];
