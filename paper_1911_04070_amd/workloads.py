@@ -69,6 +69,8 @@ WORKLOADS["cls_lengths"] = replace(WORKLOADS["cls"], name="cls_lengths", index=6
 # forward only, as in the paper's inference throughput comparison (Sec. 4.4)
 WORKLOADS["lm_infer"] = replace(WORKLOADS["lm"], name="lm_infer", backward=False)
 WORKLOADS["lm_lengths"] = replace(WORKLOADS["lm"], name="lm_lengths", index=7, B=8, length_mix="reviews")
+# the density of the paper's character-level language models (Sec. 4.2: k = 64 on contexts of 8192)
+WORKLOADS["charlm"] = replace(WORKLOADS["lm"], name="charlm", index=8, k=64)
 
 
 def make_lengths(w: Workload) -> np.ndarray:

@@ -169,7 +169,7 @@ def test_large_density_on_key_tiles(n, k, causal):
     run_case(Workload("dense_k", 11, n, k, causal, 1, 2, 64, "bf16", True))
 
 
-FULL = ["cls", "lm", "xl", "ksweep2", "ksweep4", "ksweep8", "ksweep16", "ksweep32"]
+FULL = ["cls", "lm", "xl", "ksweep2", "ksweep4", "ksweep8", "ksweep16", "ksweep32", "charlm"]
 
 
 @pytest.mark.parametrize("name", FULL)
