@@ -249,7 +249,8 @@ int bpt_layer_bwd(const bpt_graph_t* g, int32_t B, int32_t H, float scale, const
  * root is still node 2n-2 (it is kept by every sequence with a token) and token rows past a
  * sequence's end hold unspecified values.  The workspace (bpt_stack_fwd_workspace bytes of
  * device memory) keeps every layer's input states and activations for bpt_stack_bwd; nothing
- * is allocated beyond what bpt_layer_fwd states.  num_layers <= 256. */
+ * is allocated beyond what bpt_layer_fwd states, so after one call outside a capture the call
+ * (and bpt_stack_bwd) can be captured into a HIP graph.  num_layers <= 256. */
 size_t bpt_stack_fwd_workspace(const bpt_graph_t* g, int32_t B, int32_t H, int32_t d_ff, int32_t num_layers);
 int bpt_stack_fwd(const bpt_graph_t* g, int32_t B, int32_t H, int32_t num_layers, float scale, const int32_t* seq_len,
                   const void* const* rel, const void* E, const bpt_layer_params_t* p, void* root, void* tokens,

@@ -131,3 +131,45 @@ def test_stack_outputs_are_optional():
     with pytest.raises(Exception):
         bpt.bpt_stack_fwd(g, Ed, Rd, Pd, heads, workspace=torch.empty(fws - 256, dtype=torch.uint8, device="cuda"))
     g.destroy()
+
+
+def test_stack_replays_from_a_captured_graph():
+    # after a first call outside the capture (it creates the GEMM library's handle and loads its kernels) a whole
+    # training step of the stack only launches kernels on the caller's stream: captured once and replayed with new
+    # embeddings in the same buffer, with eager work between the replays, it gives the bits of the eager call
+    n, k, causal, B, heads, d_ff = 512, 4, True, 2, 2, 256
+    E, rels, params, _, d_tokens = make_stack(n, k, causal, B, heads, d_ff, 77, False)
+    g = bpt.bpt_build_graph(n, k, causal)
+    dev = lambda a: torch.from_numpy(a).to(torch.bfloat16).cuda()
+    Ed, Rd, Pd, dT = dev(E), [dev(r) for r in rels], [to_dev(p) for p in params], dev(d_tokens)
+    fws, bws = bpt.stack_workspace_bytes(g, B, heads, d_ff, LAYERS)
+    ws_f = torch.empty(fws + 256, dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(bws + 256, dtype=torch.uint8, device="cuda")
+
+    def step():
+        _, tokens = bpt.bpt_stack_fwd(g, Ed, Rd, Pd, heads, scale=0.125, want_root=False, workspace=ws_f)
+        dE, d_rels, grads = bpt.bpt_stack_bwd(g, Ed, Rd, Pd, heads, ws_f, None, dT, scale=0.125, workspace=ws_b)
+        return [tokens, dE] + list(d_rels) + [grads[layer][name] for layer in range(LAYERS) for name in GRADS]
+
+    for _ in range(2):
+        step()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        captured = step()                     # its outputs live in the graph's memory pool
+        graph.capture_end()
+    torch.cuda.synchronize()
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    for replay in range(3):
+        Ed.copy_(torch.randn(Ed.shape, device="cuda", generator=gen).to(Ed.dtype))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [t.clone() for t in captured]
+        eager = step()
+        torch.cuda.synchronize()
+        for i, (a, b) in enumerate(zip(got, eager)):
+            assert torch.equal(a, b), (replay, i)
+    g.destroy()
