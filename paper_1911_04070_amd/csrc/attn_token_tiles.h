@@ -700,6 +700,7 @@ __global__ void __launch_bounds__(kTileThreads, DENSE ? 1 : 2) bwd_q_tile_kernel
     float2* wp_t = a.wp;   // this (batch, head)'s pairs, in tile order: [chunk][token][16 columns]
     f32x4_t ow[4], op[4];
     uint32_t rowh = 0;   // DROP: hash of (seed, batch*head, token j of the tile)
+    bool tables_clear = false;   // DENSE: w_s and p_s hold zeros
 
     while (cc.valid) {
         if (cc.pair == 0) {   // a new tile: its operands arrived with the rows of this pair
@@ -731,9 +732,11 @@ __global__ void __launch_bounds__(kTileThreads, DENSE ? 1 : 2) bwd_q_tile_kernel
                 wave_lds_sync();
                 mask_bias(a, bias_s, cc.tile * 16, seq_length_u(a.seq_len, cc.bh / a.H, a.n), g, j);
             }
-            if (DENSE)   // w_s and p_s are adjacent; the previous tile's reads ended with a wave_lds_sync
+            if (DENSE && !tables_clear) {   // w_s and p_s are adjacent; later tiles find them cleared by the reads below
                 for (int i = lane * 4; i < 32 * a.bias_stride; i += 256)
                     *reinterpret_cast<f32x4_t*>(w_s + i) = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                tables_clear = true;
+            }
         }
         wave_lds_sync();  // the previous pair's reads of k_s, v_s (and the previous tile's of bias_s) are done
 #pragma unroll
@@ -853,6 +856,11 @@ __global__ void __launch_bounds__(kTileThreads, DENSE ? 1 : 2) bwd_q_tile_kernel
                     const f32x4_t w1 = *reinterpret_cast<const f32x4_t*>(w_s + j * a.bias_stride + ks + 8 * g + 4);
                     const f32x4_t p0 = *reinterpret_cast<const f32x4_t*>(p_s + j * a.bias_stride + ks + 8 * g);
                     const f32x4_t p1 = *reinterpret_cast<const f32x4_t*>(p_s + j * a.bias_stride + ks + 8 * g + 4);
+                    // this lane is the only reader of these 8 columns of row j: it leaves them cleared for the next tile
+                    *reinterpret_cast<f32x4_t*>(w_s + j * a.bias_stride + ks + 8 * g) = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                    *reinterpret_cast<f32x4_t*>(w_s + j * a.bias_stride + ks + 8 * g + 4) = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                    *reinterpret_cast<f32x4_t*>(p_s + j * a.bias_stride + ks + 8 * g) = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                    *reinterpret_cast<f32x4_t*>(p_s + j * a.bias_stride + ks + 8 * g + 4) = f32x4_t{0.f, 0.f, 0.f, 0.f};
                     uint32_t hi[4], lo[4];
                     split_pack(w0[0] - delta * p0[0], w0[1] - delta * p0[1], hi[0], lo[0]);
                     split_pack(w0[2] - delta * p0[2], w0[3] - delta * p0[3], hi[1], lo[1]);
