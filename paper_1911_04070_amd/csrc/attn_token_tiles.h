@@ -517,9 +517,11 @@ __global__ void __launch_bounds__(kTileThreads, DENSE ? 1 : 2) bwd_q_tile_kernel
     bf16_t* v_s = k_s + 32 * kRowStride;                                // the same for V rows
     int32_t* relid_s = reinterpret_cast<int32_t*>(smem + rel_bytes + (size_t)kTileWaves * 16 * a.bias_stride * sizeof(float) +
                                                   (size_t)kTileWaves * 64 * kRowStride * sizeof(bf16_t));   // [cid_pad], DROP
-    // DENSE: w and p of the tile, [16 tokens][bias_stride] each, after relid_s
+    // DENSE: (w, p) of the tile, [16 tokens][cid_pad + 2] pairs, after relid_s (the region is sized as two tables of
+    // bias_stride floats per token; a row of cid_pad + 2 pairs puts 8 consecutive tokens on different banks)
     float* w_s = reinterpret_cast<float*>(relid_s + a.cid_pad) + (size_t)wave * 32 * a.bias_stride;
-    float* p_s = w_s + 16 * a.bias_stride;
+    float2* wp_s = reinterpret_cast<float2*>(w_s);
+    const int wp_stride = a.cid_pad + 2;
     if (DROP)
         for (int i = threadIdx.x; i < a.cid_pad; i += blockDim.x) relid_s[i] = i < a.num_cids ? a.cid_to_id[i] : 0;
     if (REL_LDS) {
@@ -700,7 +702,7 @@ __global__ void __launch_bounds__(kTileThreads, DENSE ? 1 : 2) bwd_q_tile_kernel
     float2* wp_t = a.wp;   // this (batch, head)'s pairs, in tile order: [chunk][token][16 columns]
     f32x4_t ow[4], op[4];
     uint32_t rowh = 0;   // DROP: hash of (seed, batch*head, token j of the tile)
-    bool tables_clear = false;   // DENSE: w_s and p_s hold zeros
+    bool tables_clear = false;   // DENSE: the (w, p) table holds zeros
 
     while (cc.valid) {
         if (cc.pair == 0) {   // a new tile: its operands arrived with the rows of this pair
@@ -732,7 +734,7 @@ __global__ void __launch_bounds__(kTileThreads, DENSE ? 1 : 2) bwd_q_tile_kernel
                 wave_lds_sync();
                 mask_bias(a, bias_s, cc.tile * 16, seq_length_u(a.seq_len, cc.bh / a.H, a.n), g, j);
             }
-            if (DENSE && !tables_clear) {   // w_s and p_s are adjacent; later tiles find them cleared by the reads below
+            if (DENSE && !tables_clear) {   // the whole region once; later tiles find it cleared by the reads below
                 for (int i = lane * 4; i < 32 * a.bias_stride; i += 256)
                     *reinterpret_cast<f32x4_t*>(w_s + i) = f32x4_t{0.f, 0.f, 0.f, 0.f};
                 tables_clear = true;
@@ -801,10 +803,8 @@ __global__ void __launch_bounds__(kTileThreads, DENSE ? 1 : 2) bwd_q_tile_kernel
             if (DENSE) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
-                    if (cid[c][r] >= 0) {
-                        w_s[j * a.bias_stride + cid[c][r]] = pw[c][r];
-                        p_s[j * a.bias_stride + cid[c][r]] = pp[c][r];
-                    }
+                    // a slot without an edge (w = p = 0) goes to the first padding column, which nothing reads
+                    wp_s[j * wp_stride + (cid[c][r] >= 0 ? cid[c][r] : a.cid_pad)] = make_float2(pw[c][r], pp[c][r]);
             } else {
                 // (w, p) of this lane's 4 columns: 32 contiguous bytes, a chunk is 2 KB contiguous
                 float4* dst = reinterpret_cast<float4*>(wp_t + ((int64_t)(cc.cp0 + 2 * cc.pair + c) * 16 + j) * 16 + 4 * g);
@@ -852,20 +852,17 @@ __global__ void __launch_bounds__(kTileThreads, DENSE ? 1 : 2) bwd_q_tile_kernel
                 bf16_t* ds_l = k_s + 16 * dstride;
                 // relative-position part of dQ: dS [token j][ids] x Rel [ids][features]
                 for (int ks = 0; ks < a.cid_pad; ks += 32) {
-                    const f32x4_t w0 = *reinterpret_cast<const f32x4_t*>(w_s + j * a.bias_stride + ks + 8 * g);
-                    const f32x4_t w1 = *reinterpret_cast<const f32x4_t*>(w_s + j * a.bias_stride + ks + 8 * g + 4);
-                    const f32x4_t p0 = *reinterpret_cast<const f32x4_t*>(p_s + j * a.bias_stride + ks + 8 * g);
-                    const f32x4_t p1 = *reinterpret_cast<const f32x4_t*>(p_s + j * a.bias_stride + ks + 8 * g + 4);
-                    // this lane is the only reader of these 8 columns of row j: it leaves them cleared for the next tile
-                    *reinterpret_cast<f32x4_t*>(w_s + j * a.bias_stride + ks + 8 * g) = f32x4_t{0.f, 0.f, 0.f, 0.f};
-                    *reinterpret_cast<f32x4_t*>(w_s + j * a.bias_stride + ks + 8 * g + 4) = f32x4_t{0.f, 0.f, 0.f, 0.f};
-                    *reinterpret_cast<f32x4_t*>(p_s + j * a.bias_stride + ks + 8 * g) = f32x4_t{0.f, 0.f, 0.f, 0.f};
-                    *reinterpret_cast<f32x4_t*>(p_s + j * a.bias_stride + ks + 8 * g + 4) = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                    // 8 pairs of row j, (w, p) (w, p) in every 16 bytes; this lane is their only reader and leaves them
+                    // cleared for the next tile
+                    f32x4_t* pairs = reinterpret_cast<f32x4_t*>(wp_s + j * wp_stride + ks + 8 * g);
+                    const f32x4_t x0 = pairs[0], x1 = pairs[1], x2 = pairs[2], x3 = pairs[3];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) pairs[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
                     uint32_t hi[4], lo[4];
-                    split_pack(w0[0] - delta * p0[0], w0[1] - delta * p0[1], hi[0], lo[0]);
-                    split_pack(w0[2] - delta * p0[2], w0[3] - delta * p0[3], hi[1], lo[1]);
-                    split_pack(w1[0] - delta * p1[0], w1[1] - delta * p1[1], hi[2], lo[2]);
-                    split_pack(w1[2] - delta * p1[2], w1[3] - delta * p1[3], hi[3], lo[3]);
+                    split_pack(x0[0] - delta * x0[1], x0[2] - delta * x0[3], hi[0], lo[0]);
+                    split_pack(x1[0] - delta * x1[1], x1[2] - delta * x1[3], hi[1], lo[1]);
+                    split_pack(x2[0] - delta * x2[1], x2[2] - delta * x2[3], hi[2], lo[2]);
+                    split_pack(x3[0] - delta * x3[1], x3[2] - delta * x3[3], hi[3], lo[3]);
                     const u32x4 xh = {hi[0], hi[1], hi[2], hi[3]}, xl = {lo[0], lo[1], lo[2], lo[3]};
                     const bf16x8_t aH = __builtin_bit_cast(bf16x8_t, xh), aL = __builtin_bit_cast(bf16x8_t, xl);
                     *reinterpret_cast<u32x4*>(ds_h + j * dstride + ks + 8 * g) = xh;
