@@ -28,15 +28,15 @@ HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
 # workload; the runs and their commands are in profiles/.  None where not measured.
 MEASURED_TRAFFIC = {
     "lm": {  # profiles/lm_n8192_k8_causal_bf16_kernels.md
-        "bwd_kv_tile_kernel": int((212892.0 * 2.0 + 279937.0) * 1024),
-        "bwd_q_tile_kernel": int((132656.0 * 2.0 + 77878.0) * 1024),
-        "fwd_tile_kernel": int((116144.0 * 2.0 + 36112.0) * 1024),
-        "bwd_q_span_tile_kernel": int((67592.0 * 2.0 + 105212.0) * 1024),
-        "fwd_span_tile_kernel": int((49604.0 * 2.0 + 60284.0) * 1024),
+        "bwd_kv_tile_kernel": int((212833.0 * 2.0 + 279937.0) * 1024),
+        "bwd_q_tile_kernel": int((132667.0 * 2.0 + 77826.0) * 1024),
+        "fwd_tile_kernel": int((116273.0 * 2.0 + 36091.0) * 1024),
+        "bwd_q_span_tile_kernel": int((67596.0 * 2.0 + 105082.0) * 1024),
+        "fwd_span_tile_kernel": int((49609.0 * 2.0 + 59992.0) * 1024),
     },
 }
 # HBM bytes of one whole step (all kernels, same counters and scaling)
-MEASURED_STEP_TRAFFIC = {"lm": 1852815643}
+MEASURED_STEP_TRAFFIC = {"lm": 1852491634}
 
 
 def parse():
