@@ -108,13 +108,14 @@ def bench_stack(args, w, bpt, torch, np):
     ms = wall_ms(lambda: (fwd(), bwd()))
     ms_fwd = wall_ms(fwd)
     rows = w.B * g.num_nodes
+    tokens = int(make_lengths(w).sum()) if w.length_mix else w.B * w.n   # the tokens that exist, not the padding
     flops = layers * 3 * 2.0 * rows * (4 * d * d + 2 * d * d_ff)
     print(json.dumps({
-        "metric": "BPT graph update fwd+bwd tokens/sec", "value": round(w.B * w.n / (ms * 1e-3), 1), "unit": "tokens/s",
+        "metric": "BPT graph update fwd+bwd tokens/sec", "value": round(tokens / (ms * 1e-3), 1), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
         "dtype": "bf16", "data": "synthetic", "vs_baseline": None, "forward_ms": round(ms_fwd, 4),
         "config": {"workload": "%s+%d layers" % (w.name, layers), "n": w.n, "k": w.k, "causal": w.causal, "batch": w.B,
-                   "heads": w.H, "d_model": d, "d_ff": d_ff, "layers": layers, "node_rows": rows,
+                   "heads": w.H, "d_model": d, "d_ff": d_ff, "layers": layers, "node_rows": rows, "tokens": tokens,
                    "output": "tokens" if tokens_out else "root"},
         "dense_TFLOPs": round(flops / (ms * 1e-3) / 1e12, 1),
         "workspace_GB": round((fws + bws) / 1e9, 2),
