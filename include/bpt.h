@@ -205,7 +205,9 @@ typedef struct {
  * Q, K, V, the attention output, Z and the hidden FFN activations are stored in bf16 and stay
  * in the workspace for bpt_layer_bwd.
  * workspace: device memory of at least bpt_layer_fwd_workspace bytes; nothing is allocated
- * except, once per host thread and device, the rocBLAS handle.  H * 64 <= 2048. */
+ * except, once per host thread and device, the rocBLAS handle.  H * 64 <= 2048.  Every tensor
+ * of the layer and stack calls (parameters and gradients included) starts on a 16-byte
+ * boundary, else BPT_ERR_INVALID_ARG. */
 size_t bpt_layer_fwd_workspace(const bpt_graph_t* g, int32_t B, int32_t H, int32_t d_ff);
 int bpt_layer_fwd(const bpt_graph_t* g, int32_t B, int32_t H, float scale, const int32_t* seq_len, const void* rel,
                   const void* X, const bpt_layer_params_t* p, void* Y, void* workspace, size_t workspace_bytes,

@@ -433,6 +433,13 @@ int gemm_rm(rocblas_handle h, int64_t M, int N, int K, const void* A, const void
 }
 
 size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+// the kernels here move 16 bytes per lane: every tensor has to start on a 16-byte boundary (null passes: optional
+// arguments are checked where they are used)
+template <typename... P>
+bool any_misaligned(P... p) {
+    const uintptr_t bits = (... | reinterpret_cast<uintptr_t>(static_cast<const void*>(p)));
+    return (bits & 15u) != 0;
+}
 
 struct LayerBuffers {
     size_t q, k, v, o, lse, acc1, acc2, st1, st2, z, f1, attn, total;
@@ -611,6 +618,8 @@ int bpt_layer_fwd(const bpt_graph_t* g, int32_t B, int32_t H, float scale, const
     if (!g || !rel || !X || !p || !Y || B < 1 || H < 1) return BPT_ERR_INVALID_ARG;
     if (!p->Wq || !p->Wk || !p->Wv || !p->Wo || !p->W1 || !p->W2 || !p->b1 || !p->b2 || !p->g1 || !p->beta1 || !p->g2 || !p->beta2)
         return BPT_ERR_INVALID_ARG;
+    if (any_misaligned(X, Y, workspace, p->Wq, p->Wk, p->Wv, p->Wo, p->W1, p->W2, p->b1, p->b2, p->g1, p->beta1, p->g2, p->beta2))
+        return BPT_ERR_INVALID_ARG;
     const int d = H * kD, d_ff = p->d_ff;
     if (d > 8 * 64 * kLnMaxChunks || d_ff < 8 || (d_ff & 7)) return BPT_ERR_UNSUPPORTED;
     const int64_t rows = (int64_t)B * g->num_nodes;
@@ -671,6 +680,10 @@ int bpt_layer_bwd(const bpt_graph_t* g, int32_t B, int32_t H, float scale, const
         return BPT_ERR_INVALID_ARG;
     if (!gr->dWq || !gr->dWk || !gr->dWv || !gr->dWo || !gr->dW1 || !gr->db1 || !gr->dW2 || !gr->db2 || !gr->dg1 ||
         !gr->dbeta1 || !gr->dg2 || !gr->dbeta2)
+        return BPT_ERR_INVALID_ARG;
+    if (any_misaligned(X, fwd_workspace, dY, dX, d_rel, workspace, p->Wq, p->Wk, p->Wv, p->Wo, p->W1, p->W2, p->b1, p->b2, p->g1,
+                       p->beta1, p->g2, p->beta2, gr->dWq, gr->dWk, gr->dWv, gr->dWo, gr->dW1, gr->db1, gr->dW2, gr->db2, gr->dg1,
+                       gr->dbeta1, gr->dg2, gr->dbeta2))
         return BPT_ERR_INVALID_ARG;
     const int d = H * kD, d_ff = p->d_ff;
     if (d > 8 * 64 * kLnMaxChunks || d_ff < 8 || (d_ff & 7) || d_ff > 8 * 256 * kReluChunks) return BPT_ERR_UNSUPPORTED;
@@ -765,6 +778,7 @@ int bpt_stack_fwd(const bpt_graph_t* g, int32_t B, int32_t H, int32_t num_layers
         if (p[l].d_ff != p[0].d_ff) return BPT_ERR_UNSUPPORTED;   // one workspace size serves every layer
     }
     if (p[0].d_ff < 8) return BPT_ERR_UNSUPPORTED;
+    if (any_misaligned(E, root, tokens, workspace)) return BPT_ERR_INVALID_ARG;
     const StackBuffers S = stack_buffers(g, B, H, p[0].d_ff, num_layers);
     if (S.total > workspace_bytes) return BPT_ERR_INVALID_ARG;
     const int64_t rows = (int64_t)B * g->num_nodes;
@@ -808,6 +822,7 @@ int bpt_stack_bwd(const bpt_graph_t* g, int32_t B, int32_t H, int32_t num_layers
         if (p[l].d_ff != p[0].d_ff) return BPT_ERR_UNSUPPORTED;
     }
     if (p[0].d_ff < 8) return BPT_ERR_UNSUPPORTED;
+    if (any_misaligned(fwd_workspace, d_root, d_tokens, dE, workspace)) return BPT_ERR_INVALID_ARG;
     const StackBuffers S = stack_buffers(g, B, H, p[0].d_ff, num_layers);
     if (S.total > fwd_workspace_bytes) return BPT_ERR_INVALID_ARG;
     const size_t need = bpt_stack_bwd_workspace(g, B, H, p[0].d_ff);

@@ -141,3 +141,19 @@ def test_layer_backward(n, k, causal, B, heads, d_ff, lengths, decisive):
     for name in ("db1", "db2", "dg1", "dbeta1", "dg2", "dbeta2"):
         assert torch.equal(grads[name], grads2[name]), name
     g.destroy()
+
+
+def test_misaligned_tensors_are_refused():
+    # the kernels move 16 bytes per lane: a tensor that starts 2 bytes off is an error, not a fault
+    n, k, B, heads, d_ff = 64, 2, 1, 1, 64
+    X, Rel, p = make_case(n, k, False, B, heads, d_ff, 5, True)
+    g = bpt.bpt_build_graph(n, k, False)
+    Rd, pd = torch.from_numpy(Rel).to(torch.bfloat16).cuda(), to_dev(p)
+    flat = torch.zeros(X.size + 8, dtype=torch.bfloat16, device="cuda")
+    Xd = flat[1:1 + X.size].view(X.shape)
+    assert Xd.data_ptr() % 16 == 2 and Xd.is_contiguous()
+    with pytest.raises(bpt.BptError):
+        bpt.bpt_layer_fwd(g, Xd, Rd, pd, heads)
+    bpt.bpt_layer_fwd(g, flat[8:8 + X.size].view(X.shape), Rd, pd, heads)     # 16 bytes off: fine
+    torch.cuda.synchronize()
+    g.destroy()
