@@ -23,20 +23,41 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
-# HBM bytes per launch of a kernel, from rocprofv3 FETCH_SIZE (x2.0: the counter reads half the bytes of a
-# plain device copy of known size, `--calibrate-copy-mib`) + WRITE_SIZE on this
-# workload; the runs and their commands are in profiles/.  None where not measured.
-MEASURED_TRAFFIC = {
-    "lm": {  # profiles/lm_n8192_k8_causal_bf16_kernels.md
-        "bwd_kv_tile_kernel": int((212833.0 * 2.0 + 279937.0) * 1024),
-        "bwd_q_tile_kernel": int((132667.0 * 2.0 + 77826.0) * 1024),
-        "fwd_tile_kernel": int((116273.0 * 2.0 + 36091.0) * 1024),
-        "bwd_q_span_tile_kernel": int((67596.0 * 2.0 + 105082.0) * 1024),
-        "fwd_span_tile_kernel": int((49609.0 * 2.0 + 59992.0) * 1024),
-    },
-}
-# HBM bytes of one whole step (all kernels, same counters and scaling)
-MEASURED_STEP_TRAFFIC = {"lm": 1852491634}
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 matrix-core peak, published
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+KERNEL_SOURCES = os.path.join(ROOT, "paper_1911_04070_amd", "csrc")
+
+
+def kernel_source_hash():
+    """sha256 over the kernel sources: the counter figures in profiles/ belong to one build of the kernels."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(KERNEL_SOURCES)):
+        if name.endswith((".h", ".hip")):
+            with open(os.path.join(KERNEL_SOURCES, name), "rb") as f:
+                h.update(name.encode() + b"\0" + f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload):
+    """HBM bytes per launch of every kernel of `workload` from profiles/hbm_traffic.txt (rocprofv3 FETCH_SIZE and
+    WRITE_SIZE runs, scaled as that file says), with the hash of the kernel sources they were taken on.
+    Returns ({kernel: (bytes read, bytes written, launches per step)}, sources hash or None)."""
+    per_kernel, src, fetch_scale, write_scale = {}, None, 1.0, 1.0
+    if not os.path.exists(TRAFFIC_FILE):
+        return per_kernel, src
+    with open(TRAFFIC_FILE) as f:
+        for line in f:
+            t = line.split()
+            if not t or t[0].startswith("#"):
+                continue
+            if t[0] == "sources":
+                src = t[1]
+            elif t[0] == "scale":                       # scale FETCH_SIZE x  WRITE_SIZE y   (bytes per counted KiB / 1024)
+                fetch_scale, write_scale = float(t[2]), float(t[4])
+            elif t[0] == workload:                      # workload kernel FETCH_SIZE WRITE_SIZE launches_per_step
+                per_kernel[t[1]] = (float(t[2]) * fetch_scale * 1024.0, float(t[3]) * write_scale * 1024.0, float(t[4]))
+    return per_kernel, src
 
 
 def parse():
@@ -58,6 +79,12 @@ def parse():
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="only run a plain device-to-device copy of this many MiB (10 times) and exit: the known "
                          "traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
+    ap.add_argument("--calibrate-gather-mib", type=int, default=0,
+                    help="only run the library's calibration gather over this many MiB of 128-byte rows (10 times) and "
+                         "exit: known traffic of the attention kernels' request shape for scaling the same counters")
+    ap.add_argument("--regions", type=int, default=5,
+                    help="the timed steps are run as this many back-to-back regions (each synchronised on both sides); "
+                         "ms_per_step is the median region, the spread is reported beside it")
     return ap.parse_args()
 
 
@@ -202,6 +229,20 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_mib": args.calibrate_copy_mib, "copies": 10}), flush=True)
         return
+    if args.calibrate_gather_mib > 0:
+        # rows of 128 bytes of a tensor far larger than the caches, each read once through a random permutation
+        from paper_1911_04070_amd import binding as bpt
+        torch.cuda.set_device(0)
+        rows = (args.calibrate_gather_mib << 20) // 128
+        src = torch.ones(rows * 128, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        perm = torch.from_numpy(np.random.Generator(np.random.PCG64(1911)).permutation(rows).astype(np.int32)).cuda()
+        for _ in range(10):
+            bpt.bpt_calibrate_gather(src, perm, dst)
+        torch.cuda.synchronize()
+        print(json.dumps({"gather_mib": args.calibrate_gather_mib, "rows": rows, "launches": 10,
+                          "bytes_read_per_launch": rows * 132, "bytes_written_per_launch": rows * 128}), flush=True)
+        return
 
     from paper_1911_04070_amd import binding as bpt
     from paper_1911_04070_amd.workloads import WORKLOADS, make_inputs, make_lengths
@@ -254,12 +295,20 @@ def main():
 
     for _ in range(args.warmup):
         step()
+    # exactly --steps timed steps, as back-to-back regions with a synchronisation on both sides of each
+    regions = max(1, min(args.regions, args.steps))
+    sizes = [args.steps // regions + (1 if r < args.steps % regions else 0) for r in range(regions)]
+    region_ms = []
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    t_all = time.perf_counter()
+    for count in sizes:
+        t0 = time.perf_counter()
+        for _ in range(count):
+            step()
+        torch.cuda.synchronize()
+        region_ms.append((time.perf_counter() - t0) * 1e3 / count)
+    ms_mean = (time.perf_counter() - t_all) * 1e3 / args.steps
+    ms_per_step = float(np.median(region_ms))
 
     # per-stage device time with events on the stream the library launches on
     def timed(fn, reps):
@@ -299,13 +348,22 @@ def main():
     copy_gbs = 2.0 * src.numel() / (copy_ms * 1e-3) / 1e9
     del src, dst
 
-    # algorithmic bytes per launch: every edge-instance a gather kernel handles counts one
-    # key row + one value row (or one query row + one dout row): 256 B in bf16, 512 B in fp32
+    # ---- roofline of the dominant kernel --------------------------------------------------------------------
+    # Two byte counts per launch, never conflated:
+    #  * gathered bytes: one key row + one value row (or one query row + one dout row) per edge-instance the kernel
+    #    handles, 256 B in bf16 -- the method's per-edge work at the load level.  The tile kernels fetch a row
+    #    once per 16-row tile and re-use it on chip, so this is NOT a lower bound on memory traffic;
+    #  * compulsory bytes: every row the kernel must read or write, once -- a lower bound on its HBM traffic whatever
+    #    the blocking, so compulsory bytes / time / HBM peak is a fraction of a roof (<= 1 by construction).
     bh = w.B * w.H
+    row_ptr_h, col_h, _ = g.csr_to_host()
+    e_tok_graph = int(row_ptr_h[w.n])
     if lengths is None:
-        tok_inst = int(g.csr_to_host()[0][w.n]) * bh
+        tok_inst = e_tok_graph * bh
+        fill = 1.0
     else:   # every level above the tokens holds each token of a sequence once
         tok_inst = edge_inst - w.H * int(lengths.sum()) * (g.num_levels - 1)
+        fill = float(lengths.sum()) / float(w.B * w.n)
     span_inst = edge_inst - tok_inst
     gather = 256.0 * bytes_scale
     alg_bytes = {
@@ -318,35 +376,86 @@ def main():
         span_inst if "fwd_span_tile_kernel" in kernel_ms else 0))
     alg_bytes["bwd_q_kernel"] = gather * (edge_inst - (tok_inst if "bwd_q_tile_kernel" in kernel_ms else 0) - (
         span_inst if "bwd_q_span_tile_kernel" in kernel_ms else 0))
+    esz = 2 if w.dtype == "bf16" else 4
+    row, frow = w.D * esz, w.D * 4                            # a row of a tensor; a row of an fp32 gradient
+    # node rows per (batch, head), scaled by the fill of a batch of different lengths (the kept nodes)
+    n_tok, n_span, n_all = w.n * fill, (w.n - 1) * fill, g.num_nodes * fill
+    keys_tok = len(np.unique(col_h[:e_tok_graph])) * fill     # nodes some token row attends to
+    keyed = len(np.unique(col_h)) * fill                      # nodes with at least one in-edge
+    compulsory_kernel = {
+        # Q rows, K and V rows, out rows, lse
+        "fwd_tile_kernel": bh * (n_tok * row + keys_tok * 2 * row + n_tok * row + n_tok * 4),
+        "fwd_span_tile_kernel": bh * (n_span * row + n_tok * 2 * row + n_span * row + n_span * 4),
+        # Q and dout rows, K and V rows, lse; dQ rows (fp32) and (lse, delta) out
+        "bwd_q_tile_kernel": bh * (n_tok * 2 * row + keys_tok * 2 * row + n_tok * 4 + n_tok * frow + n_tok * 8),
+        "bwd_q_span_tile_kernel": bh * (n_span * 2 * row + n_tok * 2 * row + n_span * 4 + n_span * frow + n_span * 8),
+        # Q and dout rows of every query node with (lse, delta), K and V rows of the keys; dK and dV rows (fp32) out
+        "bwd_kv_tile_kernel": bh * (n_all * 2 * row + n_all * 8 + keyed * 2 * row + keyed * 2 * frow),
+    }
+    compulsory_kernel["bwd_kv_kernel"] = compulsory_kernel["bwd_kv_tile_kernel"]
+    rows_fwd = n_all - (n_tok if "fwd_tile_kernel" in kernel_ms else 0) - (n_span if "fwd_span_tile_kernel" in kernel_ms else 0)
+    rows_bq = n_all - (n_tok if "bwd_q_tile_kernel" in kernel_ms else 0) - (n_span if "bwd_q_span_tile_kernel" in kernel_ms else 0)
+    keys_of = lambda rows: keyed if rows > n_span else n_tok   # all rows: every keyed node; span rows only: the tokens
+    compulsory_kernel["fwd_kernel"] = bh * (rows_fwd * 2 * row + keys_of(rows_fwd) * 2 * row + rows_fwd * 4)
+    compulsory_kernel["bwd_q_kernel"] = bh * (rows_bq * 2 * row + keys_of(rows_bq) * 2 * row + rows_bq * (12 + frow))
     main = {k: v for k, v in kernel_ms.items() if k in alg_bytes}
     dominant = max(main, key=main.get)
-    achieved = alg_bytes[dominant] / (kernel_ms[dominant] * 1e-3) / 1e9
+    dom_s = kernel_ms[dominant] * 1e-3
+    achieved = compulsory_kernel[dominant] / dom_s / 1e9
     step_alg_bytes = gather * (3 if w.backward else 1) * edge_inst
-    esz = 2 if w.dtype == "bf16" else 4
-    tensor = bh * g.num_nodes * w.D
+    tensor = bh * n_all * w.D
     # the tensors of the boundary, each moved once per stage that needs it: the forward reads Q, K, V and
     # writes out, lse; the backward reads Q, K, V, dout, lse and writes dQ, dK, dV (fp32) -- no workspace traffic
-    compulsory = tensor * esz * 4 + bh * g.num_nodes * 4
+    compulsory = tensor * esz * 4 + bh * n_all * 4
     if w.backward:
-        compulsory += tensor * esz * 4 + bh * g.num_nodes * 4 + 3 * tensor * 4
+        compulsory += tensor * esz * 4 + bh * n_all * 4 + 3 * tensor * 4
+    # measured HBM traffic (rocprofv3 counters, profiles/hbm_traffic.txt) -- only if taken on these kernel sources
+    per_kernel, measured_on = measured_traffic(w.name)
+    sources = kernel_source_hash()
+    fresh = bool(per_kernel) and measured_on == sources and args.dropout == 0
+    traffic = step_traffic = None
+    if fresh:
+        if dominant in per_kernel:
+            traffic = int(per_kernel[dominant][0] + per_kernel[dominant][1])
+        step_traffic = int(sum((r + wr) * launches for r, wr, launches in per_kernel.values()))
+    # matrix-core work of the dominant kernel if its tiles were full: 2 * 64 flops per edge-instance and product
+    products = {"fwd_tile_kernel": 3, "fwd_span_tile_kernel": 2, "bwd_q_tile_kernel": 6, "bwd_q_span_tile_kernel": 4,
+                "bwd_kv_tile_kernel": 5}.get(dominant)
     roofline = {
         "bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
         "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-        "device_copy_GBs": round(copy_gbs, 1),
-        "traffic": MEASURED_TRAFFIC.get(w.name, {}).get(dominant),
+        "bytes": "compulsory: every row the kernel has to read or write, once (a lower bound on its HBM traffic)",
+        "compulsory_bytes": int(compulsory_kernel[dominant]),
+        "traffic": traffic,
+        "wasted_traffic_ratio": round(traffic / compulsory_kernel[dominant], 3) if traffic else None,
+        "traffic_GBs": round(traffic / dom_s / 1e9, 1) if traffic else None,
+        "traffic_frac_of_peak": round(traffic / dom_s / 1e9 / HBM_PEAK_GBS, 4) if traffic else None,
+        "traffic_source": ("profiles/hbm_traffic.txt" if fresh else
+                           "none for this workload" if not per_kernel else
+                           "stale: profiles/hbm_traffic.txt was taken on kernel sources %s, these are %s" % (measured_on, sources)
+                           if measured_on != sources else "not measured with dropout"),
         "launch_ms": round(kernel_ms[dominant], 4),
-        "algorithmic_bytes_per_edge_instance": gather,
+        "limiter": "latency of the chain row gather -> LDS -> matrix products -> exp -> matrix products inside a "
+                   "wavefront at two wavefronts per SIMD (counters in profiles/): neither HBM nor the matrix cores are "
+                   "saturated; hbm is the nearer of the two roofs",
+        "mfma_frac_if_tiles_were_full": (round(products * 128.0 * (alg_bytes[dominant] / gather) / dom_s / 1e12 /
+                                               MFMA_BF16_PEAK_TFLOPS, 4) if products and w.dtype == "bf16" else None),
+        "gathered_bytes_per_edge_instance": gather,
+        "gathered_GBs": round(alg_bytes[dominant] / dom_s / 1e9, 1),
+        "device_copy_GBs": round(copy_gbs, 1),
         "kernel_ms": {k: round(v, 4) for k, v in sorted(kernel_ms.items(), key=lambda kv: -kv[1])},
+        "kernel_compulsory_frac_of_hbm_peak": {k: round(compulsory_kernel[k] / (v * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+                                               for k, v in sorted(main.items(), key=lambda kv: -kv[1])},
         "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()},
-        "step_algorithmic_GBs": round(step_alg_bytes / (ms_per_step * 1e-3) / 1e9, 1),
-        "step_measured_hbm_bytes": MEASURED_STEP_TRAFFIC.get(w.name),
-        "step_measured_hbm_frac_of_peak": (round(MEASURED_STEP_TRAFFIC[w.name] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
-                                           if w.name in MEASURED_STEP_TRAFFIC else None),
+        "step_gathered_GBs": round(step_alg_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "step_compulsory_bytes": int(compulsory),
         "step_compulsory_frac_of_hbm_peak": round(compulsory / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-        "note": "achieved counts one gathered row pair per edge-instance (the algorithmic bytes of the method); the "
-                "tile kernels fetch a row once per 16-row tile and re-use it on chip, so achieved can exceed the HBM "
-                "peak while the measured HBM traffic (traffic, profiles/) stays far below it",
+        "step_traffic": step_traffic,
+        "step_traffic_frac_of_hbm_peak": (round(step_traffic / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+                                          if step_traffic else None),
+        "step_wasted_traffic_ratio": round(step_traffic / compulsory, 3) if step_traffic else None,
+        "target_50pct_of_hbm_peak_met": (bool(step_traffic / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS >= 0.5)
+                                         if step_traffic else None),
     }
 
     cpu = None
@@ -387,6 +496,8 @@ def main():
         "value": round(edge_inst / (ms_per_step * 1e-3), 1),
         "unit": "edges/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step_min": round(min(region_ms), 4), "ms_per_step_max": round(max(region_ms), 4),
+        "ms_per_step_mean": round(ms_mean, 4), "timed_regions": sizes,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "n": w.n, "k": w.k, "causal": w.causal, "batch": w.B, "heads": w.H,

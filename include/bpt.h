@@ -71,7 +71,9 @@ typedef enum { BPT_F32 = 0, BPT_BF16 = 1 } bpt_dtype_t;
 typedef enum {
     BPT_OK = 0,
     BPT_ERR_INVALID_ARG = 1, /* null pointer, k < 1, n < 2, bad stride, small workspace */
-    BPT_ERR_UNSUPPORTED = 2, /* n not a power of two, n > 2^22, k > 2^20, D != 64, dtype */
+    BPT_ERR_UNSUPPORTED = 2, /* n not a power of two, n > 2^22, k > 2^20, D != 64, dtype; attention calls also:
+                                a graph of 2^29 edges or more, a (batch, head) slab (N * stride_n elements) of
+                                2 GiB or more, a row stride of 16 MiB or more -- see bpt_attn_fwd */
     BPT_ERR_ALLOC = 3,       /* device or host allocation failed */
     BPT_ERR_LAUNCH = 4,      /* a HIP call or kernel launch failed */
     BPT_ERR_OVERFLOW = 5     /* the graph has more than INT32_MAX edges */
@@ -122,7 +124,8 @@ void bpt_graph_destroy(bpt_graph_t* g);
 
 /* Bytes of device scratch the forward / backward need for this graph and shape
  * (0 is possible).  The caller allocates it (256-byte aligned) and may reuse it
- * between calls on the same stream. */
+ * between calls on the same stream.  SIZE_MAX ((size_t)-1) if the attention calls
+ * would refuse this graph and shape (see the limits at bpt_attn_fwd). */
 size_t bpt_attn_fwd_workspace(const bpt_graph_t* g, const bpt_shape_t* s);
 size_t bpt_attn_bwd_workspace(const bpt_graph_t* g, const bpt_shape_t* s);
 
@@ -132,7 +135,13 @@ size_t bpt_attn_bwd_workspace(const bpt_graph_t* g, const bpt_shape_t* s);
  *   out_u = sum_e exp(s_e - lse_u) * v_v
  * Arithmetic is fp32 whatever the storage dtype.  Q, K, V, rel: device, read only.
  * out (tensor dtype) and lse (fp32): device, written.  workspace: device scratch
- * of at least bpt_attn_fwd_workspace bytes (may be NULL when that is 0). */
+ * of at least bpt_attn_fwd_workspace bytes (may be NULL when that is 0).
+ * Limits of every attention call (the kernels address the edge arrays and one (batch,
+ * head) slab of a tensor with 32-bit byte offsets), BPT_ERR_UNSUPPORTED beyond them: the
+ * graph has fewer than 2^29 edges (bpt_build_graph itself accepts up to INT32_MAX);
+ * N * stride_n * element size < 2 GiB; stride_n * element size < 16 MiB;
+ * B * H * N <= 2^40.  All tensor pointers start on a 16-byte boundary, else
+ * BPT_ERR_INVALID_ARG. */
 int bpt_attn_fwd(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q, const void* K,
                  const void* V, const void* rel, void* out, float* lse, void* workspace,
                  size_t workspace_bytes, void* stream);
@@ -175,9 +184,19 @@ int bpt_attn_bwd_key_side(const bpt_graph_t* g, const bpt_shape_t* s, const void
  * "name launches total_ms", NUL-terminated and truncated to `capacity`, into the host
  * buffer `buf` (may be NULL); it returns the bytes the full text needs, or -1 on a
  * HIP error.  Enabling creates events (allocations) on every launch and the state is
- * global and not thread-safe: leave it off outside measurements. */
+ * global and not thread-safe: leave it off outside measurements.  Launches on a stream
+ * that is being captured are not recorded. */
 int bpt_profile_enable(int on);
 int64_t bpt_profile_report(char* buf, size_t capacity);
+
+/* For measurements (not part of the paper's method): a gather of known HBM traffic, against which
+ * hardware counters of the attention kernels' row gathers can be scaled.  Row perm[i] (128 bytes)
+ * of src is copied to row i of dst for i < rows, with the request shape of the attention kernels (8
+ * consecutive lanes fetch one row, 16 bytes each).  With perm a permutation of 0..rows-1 and the
+ * tensors much larger than the caches, the call reads rows * 128 bytes of rows once, rows * 4
+ * bytes of indices, and writes rows * 128 bytes.  src, dst: device, 16-byte aligned, rows * 128
+ * bytes each; perm: device, rows entries in [0, rows).  rows < 2^31. */
+int bpt_calibrate_gather(const void* src, const int32_t* perm, void* dst, int64_t rows, void* stream);
 
 /* Parameters of one graph layer (Sec. 3.1, Sec. 3.3): all device pointers, owned by the caller.
  * d = H * 64.  A map is stored row-major as [inputs][outputs] and applied as y = x W; head i of
@@ -207,7 +226,8 @@ typedef struct {
  * workspace: device memory of at least bpt_layer_fwd_workspace bytes; nothing is allocated
  * except, once per host thread and device, the rocBLAS handle.  H * 64 <= 2048.  Every tensor
  * of the layer and stack calls (parameters and gradients included) starts on a 16-byte
- * boundary, else BPT_ERR_INVALID_ARG. */
+ * boundary, else BPT_ERR_INVALID_ARG.  The layer and stack workspace queries return SIZE_MAX when
+ * the attention calls would refuse the graph and shape, and the calls then BPT_ERR_UNSUPPORTED. */
 size_t bpt_layer_fwd_workspace(const bpt_graph_t* g, int32_t B, int32_t H, int32_t d_ff);
 int bpt_layer_fwd(const bpt_graph_t* g, int32_t B, int32_t H, float scale, const int32_t* seq_len, const void* rel,
                   const void* X, const bpt_layer_params_t* p, void* Y, void* workspace, size_t workspace_bytes,

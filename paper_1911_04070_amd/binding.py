@@ -23,7 +23,7 @@ EXPORTS = [
     "bpt_build_graph", "bpt_graph_info", "bpt_graph_csr", "bpt_graph_transposed", "bpt_graph_to_host",
     "bpt_graph_transposed_to_host", "bpt_graph_destroy", "bpt_attn_fwd_workspace", "bpt_attn_bwd_workspace",
     "bpt_attn_fwd", "bpt_attn_bwd", "bpt_attn_bwd_query_side", "bpt_attn_bwd_key_side", "bpt_profile_enable",
-    "bpt_profile_report", "bpt_layer_fwd_workspace", "bpt_layer_fwd", "bpt_layer_bwd_workspace", "bpt_layer_bwd",
+    "bpt_profile_report", "bpt_calibrate_gather", "bpt_layer_fwd_workspace", "bpt_layer_fwd", "bpt_layer_bwd_workspace", "bpt_layer_bwd",
     "bpt_stack_fwd_workspace", "bpt_stack_fwd", "bpt_stack_bwd_workspace", "bpt_stack_bwd",
     "bpt_count_edges", "bpt_strerror",
 ]
@@ -99,6 +99,8 @@ def load_library() -> ctypes.CDLL:
     L.bpt_profile_enable.argtypes = [ctypes.c_int]
     L.bpt_profile_report.restype = ctypes.c_int64
     L.bpt_profile_report.argtypes = [ctypes.c_char_p, sz]
+    L.bpt_calibrate_gather.restype = ctypes.c_int
+    L.bpt_calibrate_gather.argtypes = [vp, vp, vp, i64, vp]
     L.bpt_layer_fwd_workspace.restype = sz
     L.bpt_layer_fwd_workspace.argtypes = [vp, i32, i32, i32]
     L.bpt_layer_fwd.restype = ctypes.c_int
@@ -238,6 +240,15 @@ def _same_layout(ref: torch.Tensor, *others: torch.Tensor) -> None:
             raise ValueError("tensors must share shape, strides and device")
 
 
+SIZE_MAX = 2 ** 64 - 1   # a workspace query's answer for a graph / shape the calls refuse
+
+
+def _need(nbytes: int, what: str) -> int:
+    if nbytes == SIZE_MAX:
+        raise BptError(BPT_ERR_UNSUPPORTED, what)
+    return nbytes
+
+
 def _workspace(nbytes: int, device) -> Tuple[Optional[torch.Tensor], int]:
     if nbytes == 0:
         return None, 0
@@ -264,7 +275,7 @@ def bpt_attn_fwd(g: Graph, Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, re
     if lse is None:
         lse = torch.empty(Q.shape[:3], dtype=torch.float32, device=Q.device)
     _same_layout(Q, out)
-    need = int(L.bpt_attn_fwd_workspace(g.handle, ctypes.byref(shp)))
+    need = _need(int(L.bpt_attn_fwd_workspace(g.handle, ctypes.byref(shp))), "bpt_attn_fwd_workspace")
     if workspace is None:
         workspace, ws_ptr = _workspace(need, Q.device)
     else:
@@ -275,23 +286,56 @@ def bpt_attn_fwd(g: Graph, Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, re
     return out, lse
 
 
+def _check_bwd_inputs(g, shp, Q, K, V, rel, lse, dout):
+    """What the C side cannot see behind its raw pointers: dtypes, shapes and layouts of the backward's inputs."""
+    _same_layout(Q, K, V, dout)
+    if K.dtype != Q.dtype or V.dtype != Q.dtype or dout.dtype != Q.dtype or rel.dtype != Q.dtype:
+        raise ValueError("Q, K, V, dout and rel must share a dtype")
+    if tuple(rel.shape) != (g.num_levels, g.rel_width, shp.D) or not rel.is_contiguous() or rel.device != Q.device:
+        raise ValueError("rel must be contiguous [%d,%d,%d] on the tensors' device" % (g.num_levels, g.rel_width, shp.D))
+    if lse.dtype != torch.float32 or tuple(lse.shape) != tuple(Q.shape[:3]) or not lse.is_contiguous() or \
+            lse.device != Q.device:
+        raise ValueError("lse must be contiguous fp32 [B,H,N] on the tensors' device")
+
+
+def _check_grad(Q, *grads) -> None:
+    for t in grads:
+        if t.dtype != torch.float32:
+            raise ValueError("dQ, dK, dV must be float32")
+    _same_layout(Q, *grads)
+
+
+def _check_d_rel(g, shp, Q, d_rel) -> None:
+    if d_rel.dtype != torch.float32 or tuple(d_rel.shape) != (g.num_levels, g.rel_width, shp.D) or \
+            not d_rel.is_contiguous() or d_rel.device != Q.device:
+        raise ValueError("d_rel must be contiguous fp32 [%d,%d,%d] on the tensors' device"
+                         % (g.num_levels, g.rel_width, shp.D))
+
+
+def _check_bwd_workspace(L, g, shp, workspace) -> int:
+    need = _need(int(L.bpt_attn_bwd_workspace(g.handle, ctypes.byref(shp))), "bpt_attn_bwd_workspace")
+    ws_bytes = workspace.numel() * workspace.element_size()
+    if ws_bytes < need:
+        raise ValueError("the backward needs a workspace of %d bytes, got %d" % (need, ws_bytes))
+    return ws_bytes
+
+
 def _bwd_prepare(g, Q, K, V, rel, lse, dout, scale, grads, workspace, seq_len=None, dropout=None):
     L = load_library()
     shp = _shape_of(g, Q, scale, seq_len, dropout)
-    _same_layout(Q, K, V, dout)
-    if lse.dtype != torch.float32 or tuple(lse.shape) != tuple(Q.shape[:3]) or not lse.is_contiguous():
-        raise ValueError("lse must be contiguous fp32 [B,H,N]")
+    _check_bwd_inputs(g, shp, Q, K, V, rel, lse, dout)
     if grads is None:
         dQ, dK, dV = (torch.empty_strided(Q.shape, Q.stride(), dtype=torch.float32, device=Q.device)
                       for _ in range(3))
         d_rel = torch.empty((g.num_levels, g.rel_width, shp.D), dtype=torch.float32, device=Q.device)
     else:
         dQ, dK, dV, d_rel = grads
-    _same_layout(Q, dQ, dK, dV)
-    need = int(L.bpt_attn_bwd_workspace(g.handle, ctypes.byref(shp)))
+    _check_grad(Q, dQ, dK, dV)
+    _check_d_rel(g, shp, Q, d_rel)
     if workspace is None:
-        workspace, _ = _workspace(need, Q.device)
-    ws_bytes = workspace.numel() * workspace.element_size()
+        need = _need(int(L.bpt_attn_bwd_workspace(g.handle, ctypes.byref(shp))), "bpt_attn_bwd_workspace")
+        workspace, _ = _workspace(max(need, 256), Q.device)
+    ws_bytes = _check_bwd_workspace(L, g, shp, workspace)
     return L, shp, (dQ, dK, dV, d_rel), workspace, ws_bytes
 
 
@@ -313,6 +357,10 @@ def bpt_attn_bwd_query_side(g: Graph, Q, K, V, rel, lse, dout, dQ, d_rel, worksp
     """First stage of the backward: dQ, d_rel, and delta into the workspace."""
     L = load_library()
     shp = _shape_of(g, Q, scale, seq_len, dropout)
+    _check_bwd_inputs(g, shp, Q, K, V, rel, lse, dout)
+    _check_grad(Q, dQ)
+    _check_d_rel(g, shp, Q, d_rel)
+    _check_bwd_workspace(L, g, shp, workspace)
     _check(L.bpt_attn_bwd_query_side(g.handle, ctypes.byref(shp), Q.data_ptr(), K.data_ptr(), V.data_ptr(),
                                      rel.data_ptr(), lse.data_ptr(), dout.data_ptr(), dQ.data_ptr(),
                                      d_rel.data_ptr(), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
@@ -325,6 +373,9 @@ def bpt_attn_bwd_key_side(g: Graph, Q, K, V, rel, lse, dout, dK, dV, workspace, 
     """Second stage of the backward: dK, dV (reads delta from the workspace)."""
     L = load_library()
     shp = _shape_of(g, Q, scale, seq_len, dropout)
+    _check_bwd_inputs(g, shp, Q, K, V, rel, lse, dout)
+    _check_grad(Q, dK, dV)
+    _check_bwd_workspace(L, g, shp, workspace)
     _check(L.bpt_attn_bwd_key_side(g.handle, ctypes.byref(shp), Q.data_ptr(), K.data_ptr(), V.data_ptr(),
                                    rel.data_ptr(), lse.data_ptr(), dout.data_ptr(), dK.data_ptr(), dV.data_ptr(),
                                    workspace.data_ptr(),
@@ -378,7 +429,7 @@ def bpt_layer_fwd(g: Graph, X: torch.Tensor, rel: torch.Tensor, params: dict, he
     d_ff, lp, lens = _layer_args(g, X, rel, params, heads, eps, seq_len)
     if out is None:
         out = torch.empty_like(X)
-    need = int(L.bpt_layer_fwd_workspace(g.handle, X.shape[0], heads, d_ff))
+    need = _need(int(L.bpt_layer_fwd_workspace(g.handle, X.shape[0], heads, d_ff)), "bpt_layer_fwd_workspace")
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=X.device)
     _check(L.bpt_layer_fwd(g.handle, X.shape[0], heads, float(scale) if scale else 0.0, lens, rel.data_ptr(), X.data_ptr(),
@@ -390,7 +441,7 @@ def bpt_layer_fwd(g: Graph, X: torch.Tensor, rel: torch.Tensor, params: dict, he
 def layer_workspace_bytes(g: Graph, B: int, heads: int, d_ff: int) -> Tuple[int, int]:
     """Bytes of workspace bpt_layer_fwd and bpt_layer_bwd need."""
     L = load_library()
-    return (int(L.bpt_layer_fwd_workspace(g.handle, B, heads, d_ff)), int(L.bpt_layer_bwd_workspace(g.handle, B, heads, d_ff)))
+    return (_need(int(L.bpt_layer_fwd_workspace(g.handle, B, heads, d_ff)), "bpt_layer_fwd_workspace"), _need(int(L.bpt_layer_bwd_workspace(g.handle, B, heads, d_ff)), "bpt_layer_bwd_workspace"))
 
 
 def bpt_layer_bwd(g: Graph, X: torch.Tensor, rel: torch.Tensor, params: dict, heads: int, fwd_workspace: torch.Tensor,
@@ -417,7 +468,7 @@ def bpt_layer_bwd(g: Graph, X: torch.Tensor, rel: torch.Tensor, params: dict, he
         if t.dtype != torch.float32 or t.shape != params[name[1:]].shape or not t.is_contiguous() or t.device != X.device:
             raise ValueError("gradient %s must be a contiguous fp32 tensor shaped like its parameter" % name)
     lg = BptLayerGrads(*[grads[n].data_ptr() for n in GRAD_NAMES])
-    need = int(L.bpt_layer_bwd_workspace(g.handle, X.shape[0], heads, d_ff))
+    need = _need(int(L.bpt_layer_bwd_workspace(g.handle, X.shape[0], heads, d_ff)), "bpt_layer_bwd_workspace")
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=X.device)
     _check(L.bpt_layer_bwd(g.handle, X.shape[0], heads, float(scale) if scale else 0.0, lens, rel.data_ptr(), X.data_ptr(),
@@ -449,8 +500,8 @@ def _stack_args(g: Graph, E: torch.Tensor, rels, params, heads: int, eps: float,
 def stack_workspace_bytes(g: Graph, B: int, heads: int, d_ff: int, num_layers: int) -> Tuple[int, int]:
     """Bytes of workspace bpt_stack_fwd and bpt_stack_bwd need."""
     L = load_library()
-    return (int(L.bpt_stack_fwd_workspace(g.handle, B, heads, d_ff, num_layers)),
-            int(L.bpt_stack_bwd_workspace(g.handle, B, heads, d_ff)))
+    return (_need(int(L.bpt_stack_fwd_workspace(g.handle, B, heads, d_ff, num_layers)), "bpt_stack_fwd_workspace"),
+            _need(int(L.bpt_stack_bwd_workspace(g.handle, B, heads, d_ff)), "bpt_stack_bwd_workspace"))
 
 
 def bpt_stack_fwd(g: Graph, E: torch.Tensor, rels, params, heads: int, scale: Optional[float] = None, eps: float = 1e-5,
@@ -467,7 +518,7 @@ def bpt_stack_fwd(g: Graph, E: torch.Tensor, rels, params, heads: int, scale: Op
     B, d = E.shape[0], heads * 64
     root = torch.empty((B, d), dtype=E.dtype, device=E.device) if want_root else None
     tokens = torch.empty_like(E) if want_tokens else None
-    need = int(L.bpt_stack_fwd_workspace(g.handle, B, heads, d_ff, len(params)))
+    need = _need(int(L.bpt_stack_fwd_workspace(g.handle, B, heads, d_ff, len(params))), "bpt_stack_fwd_workspace")
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=E.device)
     _check(L.bpt_stack_fwd(g.handle, B, heads, len(params), float(scale) if scale else 0.0, lens, relp, E.data_ptr(), lps,
@@ -497,7 +548,7 @@ def bpt_stack_bwd(g: Graph, E: torch.Tensor, rels, params, heads: int, fwd_works
               ("Wq", "Wk", "Wv", "Wo", "W1", "b1", "W2", "b2", "g1", "beta1", "g2", "beta2")} for p in params]
     lgs = (BptLayerGrads * len(params))(*[BptLayerGrads(*[gr[n].data_ptr() for n in GRAD_NAMES]) for gr in grads])
     drp = (ctypes.c_void_p * len(rels))(*[t.data_ptr() for t in d_rels])
-    need = int(L.bpt_stack_bwd_workspace(g.handle, B, heads, d_ff))
+    need = _need(int(L.bpt_stack_bwd_workspace(g.handle, B, heads, d_ff)), "bpt_stack_bwd_workspace")
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=E.device)
     _check(L.bpt_stack_bwd(g.handle, B, heads, len(params), float(scale) if scale else 0.0, lens, relp, lps,
@@ -559,5 +610,16 @@ def bpt_profile_report() -> dict:
 def workspace_bytes(g: Graph, like: torch.Tensor, scale: Optional[float] = None) -> Tuple[int, int]:
     L = load_library()
     shp = _shape_of(g, like, scale)
-    return (int(L.bpt_attn_fwd_workspace(g.handle, ctypes.byref(shp))),
-            int(L.bpt_attn_bwd_workspace(g.handle, ctypes.byref(shp))))
+    return (_need(int(L.bpt_attn_fwd_workspace(g.handle, ctypes.byref(shp))), "bpt_attn_fwd_workspace"),
+            _need(int(L.bpt_attn_bwd_workspace(g.handle, ctypes.byref(shp))), "bpt_attn_bwd_workspace"))
+
+
+def bpt_calibrate_gather(src: torch.Tensor, perm: torch.Tensor, dst: torch.Tensor) -> None:
+    """dst row i = src row perm[i] for rows of 128 bytes: a gather of known traffic for scaling hardware counters."""
+    rows = perm.numel()
+    if perm.dtype != torch.int32 or not perm.is_contiguous() or not src.is_contiguous() or not dst.is_contiguous():
+        raise ValueError("perm must be contiguous int32, src and dst contiguous")
+    if src.numel() * src.element_size() != rows * 128 or dst.numel() * dst.element_size() != rows * 128:
+        raise ValueError("src and dst must hold one row of 128 bytes per entry of perm")
+    _check(load_library().bpt_calibrate_gather(src.data_ptr(), perm.data_ptr(), dst.data_ptr(), rows, _stream_ptr()),
+           "bpt_calibrate_gather")

@@ -736,16 +736,16 @@ int backward(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q, const vo
 extern "C" {
 
 size_t bpt_attn_fwd_workspace(const bpt_graph_t* g, const bpt_shape_t* s) {
-    if (bpt::check_shape(g, s) != BPT_OK) return 0;
+    if (bpt::check_shape(g, s) != BPT_OK) return SIZE_MAX;
     return bpt::align_up((size_t)s->B * s->H *
                          std::max<size_t>(std::max(g->fwd.num_part, g->fwd_span.num_part), bpt::span_partials(g)) *
                          bpt::kPartStride * sizeof(float));
 }
 
 size_t bpt_attn_bwd_workspace(const bpt_graph_t* g, const bpt_shape_t* s) {
-    if (bpt::check_shape(g, s) != BPT_OK) return 0;
+    if (bpt::check_shape(g, s) != BPT_OK) return SIZE_MAX;
     bpt::BwdPlan p;
-    if (bpt::plan_bwd(g, s, &p) != BPT_OK) return 0;
+    if (bpt::plan_bwd(g, s, &p) != BPT_OK) return SIZE_MAX;
     return p.total;
 }
 
@@ -758,6 +758,7 @@ int bpt_attn_fwd(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q, cons
         bpt::misaligned(out) || bpt::misaligned(workspace))
         return BPT_ERR_INVALID_ARG;
     const size_t need = bpt_attn_fwd_workspace(g, s);
+    if (need == SIZE_MAX) return BPT_ERR_UNSUPPORTED;
     if (need > 0 && (!workspace || workspace_bytes < need)) return BPT_ERR_INVALID_ARG;
     bpt::AttnArgs a;
     bpt::fill_common(a, g, s);

@@ -611,19 +611,78 @@ void clear() {
 }
 }  // namespace
 bool enabled() { return g_on; }
+namespace {
+bool g_open = false;   // begin() has pushed a record that end() still has to close
+}
 void begin(const char* name, hipStream_t st) {
+    g_open = false;
+    // no events inside a stream capture: they would become nodes of the captured graph
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cap) != hipSuccess) {
+        (void)hipGetLastError();
+        return;
+    }
+    if (cap != hipStreamCaptureStatusNone) return;
     Rec r{name, nullptr, nullptr};
-    if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) return;
-    (void)hipEventRecord(r.a, st);
+    if (hipEventCreate(&r.a) != hipSuccess) {
+        (void)hipGetLastError();
+        return;
+    }
+    if (hipEventCreate(&r.b) != hipSuccess) {
+        (void)hipGetLastError();
+        (void)hipEventDestroy(r.a);
+        return;
+    }
+    if (hipEventRecord(r.a, st) != hipSuccess) {
+        (void)hipGetLastError();
+        (void)hipEventDestroy(r.a);
+        (void)hipEventDestroy(r.b);
+        return;
+    }
     g_recs.push_back(r);
+    g_open = true;
 }
 void end(hipStream_t st) {
-    if (!g_recs.empty()) (void)hipEventRecord(g_recs.back().b, st);
+    if (!g_open) return;   // begin() made no record for this launch: nothing of an earlier launch is touched
+    g_open = false;
+    if (hipEventRecord(g_recs.back().b, st) != hipSuccess) {
+        (void)hipGetLastError();
+        (void)hipEventDestroy(g_recs.back().a);
+        (void)hipEventDestroy(g_recs.back().b);
+        g_recs.pop_back();
+    }
 }
 }  // namespace prof
 }  // namespace bpt
 
+namespace bpt {
+namespace {
+// Rows of 128 bytes read once each through a list of row numbers, 8 consecutive lanes per row and 16 bytes per
+// lane -- the request shape of the attention kernels' row gathers -- and written back in list order.
+__global__ void __launch_bounds__(256) calibrate_gather_kernel(const uint4* __restrict__ src, const int32_t* __restrict__ perm,
+                                                               uint4* __restrict__ dst, int64_t rows) {
+    const int64_t slot = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t r = slot >> 3;
+    if (r >= rows) return;
+    const int piece = (int)(slot & 7);
+    dst[r * 8 + piece] = src[(int64_t)perm[r] * 8 + piece];
+}
+}  // namespace
+}  // namespace bpt
+
 extern "C" {
+
+int bpt_calibrate_gather(const void* src, const int32_t* perm, void* dst, int64_t rows, void* stream) {
+    if (!src || !perm || !dst || rows < 1 || rows > ((int64_t)1 << 31) - 1) return BPT_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15u) return BPT_ERR_INVALID_ARG;
+    const int64_t blocks = (rows * 8 + 255) / 256;
+    if (blocks > INT32_MAX) return BPT_ERR_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    BPT_LAUNCH("calibrate_gather_kernel", bpt::calibrate_gather_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
+               static_cast<const uint4*>(src), perm, static_cast<uint4*>(dst), rows);
+    BPT_HIP(hipGetLastError());
+    return BPT_OK;
+}
 
 int bpt_profile_enable(int on) {
     bpt::prof::clear();

@@ -593,7 +593,8 @@ StackBuffers stack_buffers(const bpt_graph* g, int B, int H, int d_ff, int num_l
     const bpt_shape_t s = attn_shape(g, B, H, 0.f, nullptr);
     StackBuffers S;
     S.state_bytes = align_up((size_t)B * g->num_nodes * H * kD * 2);
-    S.layer_bytes = align_up(layer_buffers(g, B, H, d_ff, bpt_attn_fwd_workspace(g, &s)).total);
+    const size_t attn_ws = bpt_attn_fwd_workspace(g, &s);
+    S.layer_bytes = align_up(layer_buffers(g, B, H, d_ff, attn_ws == SIZE_MAX ? 0 : attn_ws).total);
     S.layers_at = S.state_bytes * ((size_t)num_layers + 1);
     S.total = S.layers_at + S.layer_bytes * (size_t)num_layers;
     return S;
@@ -610,7 +611,9 @@ extern "C" {
 size_t bpt_layer_fwd_workspace(const bpt_graph_t* g, int32_t B, int32_t H, int32_t d_ff) {
     if (!g || B < 1 || H < 1 || d_ff < 8) return 0;
     const bpt_shape_t s = attn_shape(g, B, H, 0.f, nullptr);
-    return layer_buffers(g, B, H, d_ff, bpt_attn_fwd_workspace(g, &s)).total;
+    const size_t attn_ws = bpt_attn_fwd_workspace(g, &s);
+    if (attn_ws == SIZE_MAX) return SIZE_MAX;   // the attention calls refuse this graph and shape
+    return layer_buffers(g, B, H, d_ff, attn_ws).total;
 }
 
 int bpt_layer_fwd(const bpt_graph_t* g, int32_t B, int32_t H, float scale, const int32_t* seq_len, const void* rel,
@@ -626,6 +629,7 @@ int bpt_layer_fwd(const bpt_graph_t* g, int32_t B, int32_t H, float scale, const
     if (rows > INT32_MAX) return BPT_ERR_UNSUPPORTED;
     const bpt_shape_t s = attn_shape(g, B, H, scale, seq_len);
     const size_t attn_ws = bpt_attn_fwd_workspace(g, &s);
+    if (attn_ws == SIZE_MAX) return BPT_ERR_UNSUPPORTED;
     const LayerBuffers L = layer_buffers(g, B, H, d_ff, attn_ws);
     if (L.total > workspace_bytes || (L.total && !workspace)) return BPT_ERR_INVALID_ARG;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -668,7 +672,9 @@ int bpt_layer_fwd(const bpt_graph_t* g, int32_t B, int32_t H, float scale, const
 size_t bpt_layer_bwd_workspace(const bpt_graph_t* g, int32_t B, int32_t H, int32_t d_ff) {
     if (!g || B < 1 || H < 1 || d_ff < 8) return 0;
     const bpt_shape_t s = attn_shape(g, B, H, 0.f, nullptr);
-    return layer_bwd_buffers(g, B, H, d_ff, bpt_attn_bwd_workspace(g, &s)).total;
+    const size_t attn_ws = bpt_attn_bwd_workspace(g, &s);
+    if (attn_ws == SIZE_MAX) return SIZE_MAX;
+    return layer_bwd_buffers(g, B, H, d_ff, attn_ws).total;
 }
 
 int bpt_layer_bwd(const bpt_graph_t* g, int32_t B, int32_t H, float scale, const int32_t* seq_len, const void* rel,
@@ -690,9 +696,11 @@ int bpt_layer_bwd(const bpt_graph_t* g, int32_t B, int32_t H, float scale, const
     const int64_t rows = (int64_t)B * g->num_nodes;
     if (rows > INT32_MAX) return BPT_ERR_UNSUPPORTED;
     const bpt_shape_t s = attn_shape(g, B, H, scale, seq_len);
-    const LayerBuffers F = layer_buffers(g, B, H, d_ff, bpt_attn_fwd_workspace(g, &s));
-    if (F.total > fwd_workspace_bytes) return BPT_ERR_INVALID_ARG;
+    const size_t attn_fws = bpt_attn_fwd_workspace(g, &s);
     const size_t attn_ws = bpt_attn_bwd_workspace(g, &s);
+    if (attn_fws == SIZE_MAX || attn_ws == SIZE_MAX) return BPT_ERR_UNSUPPORTED;
+    const LayerBuffers F = layer_buffers(g, B, H, d_ff, attn_fws);
+    if (F.total > fwd_workspace_bytes) return BPT_ERR_INVALID_ARG;
     const LayerBwdBuffers L = layer_bwd_buffers(g, B, H, d_ff, attn_ws);
     if (L.total > workspace_bytes || !workspace) return BPT_ERR_INVALID_ARG;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -764,6 +772,7 @@ int bpt_layer_bwd(const bpt_graph_t* g, int32_t B, int32_t H, float scale, const
 
 size_t bpt_stack_fwd_workspace(const bpt_graph_t* g, int32_t B, int32_t H, int32_t d_ff, int32_t num_layers) {
     if (!g || B < 1 || H < 1 || d_ff < 8 || num_layers < 1 || num_layers > kMaxStackLayers) return 0;
+    if (bpt_layer_fwd_workspace(g, B, H, d_ff) == SIZE_MAX) return SIZE_MAX;
     return stack_buffers(g, B, H, d_ff, num_layers).total;
 }
 
@@ -806,6 +815,7 @@ int bpt_stack_fwd(const bpt_graph_t* g, int32_t B, int32_t H, int32_t num_layers
 size_t bpt_stack_bwd_workspace(const bpt_graph_t* g, int32_t B, int32_t H, int32_t d_ff) {
     if (!g || B < 1 || H < 1 || d_ff < 8) return 0;
     const size_t layer = bpt_layer_bwd_workspace(g, B, H, d_ff);
+    if (layer == SIZE_MAX) return SIZE_MAX;
     return layer ? 2 * align_up((size_t)B * g->num_nodes * H * kD * 2) + layer : 0;
 }
 
@@ -826,6 +836,7 @@ int bpt_stack_bwd(const bpt_graph_t* g, int32_t B, int32_t H, int32_t num_layers
     const StackBuffers S = stack_buffers(g, B, H, p[0].d_ff, num_layers);
     if (S.total > fwd_workspace_bytes) return BPT_ERR_INVALID_ARG;
     const size_t need = bpt_stack_bwd_workspace(g, B, H, p[0].d_ff);
+    if (need == SIZE_MAX) return BPT_ERR_UNSUPPORTED;
     if (!need || need > workspace_bytes) return BPT_ERR_INVALID_ARG;
     const int64_t rows = (int64_t)B * g->num_nodes;
     if (rows > INT32_MAX) return BPT_ERR_UNSUPPORTED;

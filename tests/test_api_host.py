@@ -61,8 +61,10 @@ def test_null_graph_is_an_error_everywhere():
     assert lib.bpt_graph_transposed(None, None, None, None) == bpt.BPT_ERR_INVALID_ARG
     assert lib.bpt_graph_to_host(None, None, None, None) == bpt.BPT_ERR_INVALID_ARG
     assert lib.bpt_graph_transposed_to_host(None, None, None, None) == bpt.BPT_ERR_INVALID_ARG
-    assert lib.bpt_attn_fwd_workspace(None, ctypes.byref(shp)) == 0
-    assert lib.bpt_attn_bwd_workspace(None, ctypes.byref(shp)) == 0
+    # a refused graph / shape is told apart from "no workspace needed": SIZE_MAX, not 0
+    assert lib.bpt_attn_fwd_workspace(None, ctypes.byref(shp)) == 2 ** 64 - 1
+    assert lib.bpt_attn_bwd_workspace(None, ctypes.byref(shp)) == 2 ** 64 - 1
+    assert lib.bpt_calibrate_gather(None, None, None, 8, None) == bpt.BPT_ERR_INVALID_ARG
     assert lib.bpt_attn_fwd(None, ctypes.byref(shp), *([None] * 7), 0, None) == bpt.BPT_ERR_INVALID_ARG
     assert lib.bpt_attn_bwd(None, ctypes.byref(shp), *([None] * 11), 0, None) == bpt.BPT_ERR_INVALID_ARG
     assert lib.bpt_attn_bwd_query_side(None, ctypes.byref(shp), *([None] * 9), 0, None) == bpt.BPT_ERR_INVALID_ARG
