@@ -76,7 +76,8 @@ typedef enum {
                                 2 GiB or more, a row stride of 16 MiB or more -- see bpt_attn_fwd */
     BPT_ERR_ALLOC = 3,       /* device or host allocation failed */
     BPT_ERR_LAUNCH = 4,      /* a HIP call or kernel launch failed */
-    BPT_ERR_OVERFLOW = 5     /* the graph has more than INT32_MAX edges */
+    BPT_ERR_OVERFLOW = 5,    /* the graph has more than INT32_MAX edges */
+    BPT_ERR_SCRATCH = 6      /* bpt_attn_fwd_static: the shape needs more than BPT_STATIC_SCRATCH_BYTES of scratch */
 } bpt_status_t;
 
 typedef struct {
@@ -145,6 +146,24 @@ size_t bpt_attn_bwd_workspace(const bpt_graph_t* g, const bpt_shape_t* s);
 int bpt_attn_fwd(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q, const void* K,
                  const void* V, const void* rel, void* out, float* lse, void* workspace,
                  size_t workspace_bytes, void* stream);
+
+/* bpt_attn_fwd for callers that cannot allocate device memory or hand over a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results
+ * and kernels as bpt_attn_fwd, but the scratch (partial results of span rows that are cut over
+ * several workgroups) lives in a buffer of BPT_STATIC_SCRATCH_BYTES that is part of the library's
+ * device code: nothing is allocated or freed, by this call or by anything it calls, and no
+ * workspace is passed.  Every device the library is loaded on holds the buffer until the process
+ * ends.  A graph and shape whose bpt_attn_fwd_workspace exceeds the buffer is refused with
+ * BPT_ERR_SCRATCH (e.g. n = 65536 with 8 heads; n = 8192 with 4 x 8 heads needs 17 MB and fits).
+ * g must have been built on the current device (BPT_ERR_INVALID_ARG otherwise); the buffer's address
+ * is looked up in bpt_build_graph, so a call under graph capture does no look-up either.  All calls
+ * on one device share the one buffer: calls that may overlap on a device (different streams, or
+ * host threads without an ordering between their streams) race on it and must be serialised by the
+ * caller.  The buffer keeps the previous call's contents; the forward writes every partial before it
+ * reads it, so nothing needs clearing. */
+#define BPT_STATIC_SCRATCH_BYTES (32u << 20)
+int bpt_attn_fwd_static(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q, const void* K,
+                        const void* V, const void* rel, void* out, float* lse, void* stream);
 
 /* Gradient of eq. (8) given dout = dL/dout.  With p_e = exp(s_e - lse_u),
  * dP_e = dout_u . v_v, delta_u = sum_e p_e dP_e (= dout_u . out_u), dS_e = p_e (dP_e - delta_u):

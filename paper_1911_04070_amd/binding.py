@@ -17,12 +17,13 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libbpt.so")
 
 BPT_F32, BPT_BF16 = 0, 1
-BPT_OK, BPT_ERR_INVALID_ARG, BPT_ERR_UNSUPPORTED, BPT_ERR_ALLOC, BPT_ERR_LAUNCH, BPT_ERR_OVERFLOW = range(6)
+BPT_OK, BPT_ERR_INVALID_ARG, BPT_ERR_UNSUPPORTED, BPT_ERR_ALLOC, BPT_ERR_LAUNCH, BPT_ERR_OVERFLOW, BPT_ERR_SCRATCH = range(7)
+BPT_STATIC_SCRATCH_BYTES = 32 << 20
 
 EXPORTS = [
     "bpt_build_graph", "bpt_graph_info", "bpt_graph_csr", "bpt_graph_transposed", "bpt_graph_to_host",
     "bpt_graph_transposed_to_host", "bpt_graph_destroy", "bpt_attn_fwd_workspace", "bpt_attn_bwd_workspace",
-    "bpt_attn_fwd", "bpt_attn_bwd", "bpt_attn_bwd_query_side", "bpt_attn_bwd_key_side", "bpt_profile_enable",
+    "bpt_attn_fwd", "bpt_attn_fwd_static", "bpt_attn_bwd", "bpt_attn_bwd_query_side", "bpt_attn_bwd_key_side", "bpt_profile_enable",
     "bpt_profile_report", "bpt_calibrate_gather", "bpt_layer_fwd_workspace", "bpt_layer_fwd", "bpt_layer_bwd_workspace", "bpt_layer_bwd",
     "bpt_stack_fwd_workspace", "bpt_stack_fwd", "bpt_stack_bwd_workspace", "bpt_stack_bwd",
     "bpt_count_edges", "bpt_strerror",
@@ -89,6 +90,8 @@ def load_library() -> ctypes.CDLL:
     L.bpt_attn_bwd_workspace.argtypes = [vp, P(BptShape)]
     L.bpt_attn_fwd.restype = ctypes.c_int
     L.bpt_attn_fwd.argtypes = [vp, P(BptShape), vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.bpt_attn_fwd_static.restype = ctypes.c_int
+    L.bpt_attn_fwd_static.argtypes = [vp, P(BptShape), vp, vp, vp, vp, vp, vp, vp]
     L.bpt_attn_bwd.restype = ctypes.c_int
     L.bpt_attn_bwd.argtypes = [vp, P(BptShape)] + [vp] * 11 + [sz, vp]
     L.bpt_attn_bwd_query_side.restype = ctypes.c_int
@@ -283,6 +286,25 @@ def bpt_attn_fwd(g: Graph, Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, re
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(L.bpt_attn_fwd(g.handle, ctypes.byref(shp), Q.data_ptr(), K.data_ptr(), V.data_ptr(), rel.data_ptr(),
                           out.data_ptr(), lse.data_ptr(), ws_ptr, ws_bytes, _stream_ptr()), "bpt_attn_fwd")
+    return out, lse
+
+
+def bpt_attn_fwd_static(g: Graph, Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, rel: torch.Tensor,
+                        out: torch.Tensor, lse: torch.Tensor, scale: Optional[float] = None,
+                        seq_len: Optional[torch.Tensor] = None, dropout: Optional[Tuple[float, int]] = None):
+    """bpt_attn_fwd into caller-provided out and lse with the library's static scratch: this wrapper and the call
+    allocate nothing."""
+    L = load_library()
+    shp = _shape_of(g, Q, scale, seq_len, dropout)
+    _same_layout(Q, K, V, out)
+    if K.dtype != Q.dtype or V.dtype != Q.dtype or rel.dtype != Q.dtype or out.dtype != Q.dtype:
+        raise ValueError("Q, K, V, rel and out must share a dtype")
+    if tuple(rel.shape) != (g.num_levels, g.rel_width, shp.D) or not rel.is_contiguous():
+        raise ValueError("rel must be contiguous [%d,%d,%d]" % (g.num_levels, g.rel_width, shp.D))
+    if lse.dtype != torch.float32 or tuple(lse.shape) != tuple(Q.shape[:3]) or not lse.is_contiguous():
+        raise ValueError("lse must be contiguous fp32 [B,H,N]")
+    _check(L.bpt_attn_fwd_static(g.handle, ctypes.byref(shp), Q.data_ptr(), K.data_ptr(), V.data_ptr(), rel.data_ptr(),
+                                 out.data_ptr(), lse.data_ptr(), _stream_ptr()), "bpt_attn_fwd_static")
     return out, lse
 
 

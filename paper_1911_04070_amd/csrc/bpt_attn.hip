@@ -5,6 +5,7 @@
 // lays out the workspace, launches, and exports the C entry points of bpt.h.
 #include <algorithm>
 #include <cmath>
+#include <mutex>
 
 #include "attn_device.h"
 #include "attn_gather.h"
@@ -12,7 +13,34 @@
 #include "attn_span_tiles.h"
 #include "attn_key_tiles.h"
 
+// Scratch of bpt_attn_fwd_static: device memory that belongs to the library's code object, so that the call
+// needs no allocation.  Every device the library is loaded on holds its own copy at its own address; the name
+// below is only the host-side handle of the symbol -- device code and HIP calls get the address that
+// hipGetSymbolAddress returns for the current device (static_scratch()).
+constexpr size_t kStaticScratchBytes = (size_t)BPT_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace bpt {
+namespace {
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];      // per device: address of that device's copy of `scratch`
+std::mutex g_scratch_mutex;
+}  // namespace
+
+// Address of the current device's copy of the static scratch (resolved once per device; `device` must be current).
+int static_scratch(int device, void** out) {
+    if (device < 0 || device >= kMaxDevices) return BPT_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void* ptr = nullptr;
+        BPT_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return BPT_ERR_LAUNCH;
+        g_scratch_ptr[device] = ptr;
+    }
+    *out = g_scratch_ptr[device];
+    return BPT_OK;
+}
+
 namespace {
 
 // ---- host side --------------------------------------------------------------------
@@ -775,6 +803,22 @@ int bpt_attn_fwd(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q, cons
     bpt::use_schedule(a, g->fwd);
     hipStream_t st = static_cast<hipStream_t>(stream);
     return s->dtype == BPT_BF16 ? bpt::run_fwd<bpt::bf16_t>(g, a, st) : bpt::run_fwd<float>(g, a, st);
+}
+
+int bpt_attn_fwd_static(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q, const void* K, const void* V,
+                        const void* rel, void* out, float* lse, void* stream) {
+    int rc = bpt::check_shape(g, s);
+    if (rc) return rc;
+    const size_t need = bpt_attn_fwd_workspace(g, s);
+    if (need == SIZE_MAX) return BPT_ERR_UNSUPPORTED;
+    if (need > kStaticScratchBytes) return BPT_ERR_SCRATCH;
+    int device = -1;
+    BPT_HIP(hipGetDevice(&device));
+    if (device != g->device) return BPT_ERR_INVALID_ARG;   // the scratch used is the current device's
+    void* ws = nullptr;
+    if ((rc = bpt::static_scratch(device, &ws))) return rc;
+    // the forward's kernels write every partial they later read, so nothing has to be cleared between calls
+    return bpt_attn_fwd(g, s, Q, K, V, rel, out, lse, ws, kStaticScratchBytes, stream);
 }
 
 int bpt_attn_bwd(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q, const void* K, const void* V,

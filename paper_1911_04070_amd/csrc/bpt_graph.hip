@@ -749,6 +749,9 @@ int bpt_build_graph(int32_t n, int32_t k, int32_t causal, void* stream, bpt_grap
     int rc;
     try {
         rc = bpt::build(n, k, causal, static_cast<hipStream_t>(stream), g);
+        // set-up is also where the address of this device's static scratch is looked up (bpt_attn_fwd_static)
+        void* scratch_ptr = nullptr;
+        if (rc == BPT_OK) rc = bpt::static_scratch(g->device, &scratch_ptr);
     } catch (const std::bad_alloc&) {
         rc = BPT_ERR_ALLOC;
     }
@@ -852,6 +855,7 @@ const char* bpt_strerror(int status) {
         case BPT_ERR_ALLOC: return "allocation failed";
         case BPT_ERR_LAUNCH: return "HIP call or kernel launch failed";
         case BPT_ERR_OVERFLOW: return "graph has more than INT32_MAX edges";
+        case BPT_ERR_SCRATCH: return "the call needs more scratch than the library's static buffer holds";
         default: return "unknown status";
     }
 }

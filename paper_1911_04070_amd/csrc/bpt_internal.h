@@ -92,6 +92,8 @@ struct bpt_graph {
 };
 
 namespace bpt {
+// bpt_attn.hip: address of the current device's copy of the library's static scratch, resolved on first use
+int static_scratch(int device, void** out);
 // bpt_tiles.hip: token tiles and key tiles of a graph whose CSR is on the device
 int build_tile_metadata(bpt_graph* g, const int32_t* cnt_l, const int32_t* min_l, const int32_t* cnt_r,
                         const int32_t* min_r, hipStream_t st);

@@ -33,7 +33,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_strerror_is_total():
     seen = set()
-    for code in range(0, 6):
+    for code in range(0, 7):
         msg = bpt.strerror(code)
         assert msg and msg not in seen
         seen.add(msg)
@@ -66,6 +66,7 @@ def test_null_graph_is_an_error_everywhere():
     assert lib.bpt_attn_bwd_workspace(None, ctypes.byref(shp)) == 2 ** 64 - 1
     assert lib.bpt_calibrate_gather(None, None, None, 8, None) == bpt.BPT_ERR_INVALID_ARG
     assert lib.bpt_attn_fwd(None, ctypes.byref(shp), *([None] * 7), 0, None) == bpt.BPT_ERR_INVALID_ARG
+    assert lib.bpt_attn_fwd_static(None, ctypes.byref(shp), *([None] * 7)) == bpt.BPT_ERR_INVALID_ARG
     assert lib.bpt_attn_bwd(None, ctypes.byref(shp), *([None] * 11), 0, None) == bpt.BPT_ERR_INVALID_ARG
     assert lib.bpt_attn_bwd_query_side(None, ctypes.byref(shp), *([None] * 9), 0, None) == bpt.BPT_ERR_INVALID_ARG
     assert lib.bpt_attn_bwd_key_side(None, ctypes.byref(shp), *([None] * 9), 0, None) == bpt.BPT_ERR_INVALID_ARG
