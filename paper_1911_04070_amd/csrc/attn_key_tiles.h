@@ -32,6 +32,7 @@ struct KeyArgs {
     int32_t row_bytes;
     uint32_t slab_bytes;
     const int32_t *tile_node0, *tile_info, *cols, *task_tile, *task_c0, *task_nch, *task_part;
+    const int32_t *task_ntiles, *chunk_ptr;   // chained tasks: tiles the task walks, first chunk of every tile
     const int16_t* map;
     int32_t num_tasks, num_part, num_chunks, nb_pad, W, zero;
     const int32_t* seq_len;   // [B] tokens of every sequence, or null
@@ -328,6 +329,281 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyA
                     *reinterpret_cast<float4*>(dst) = v;
             }
         }
+        wave_lds_sync();
+    }
+}
+
+// The same products for the graphs whose key tiles meet at most 32 relative-position ids, with two changes
+// that matter for the fine levels, where a tile has only one to four pairs of chunks and the start of a task
+// (task counter, tile description, column ids, first rows: four dependent round trips to memory) costs more
+// than its products.  (1) A task walks `task_ntiles` consecutive tiles of one level: their chunks are
+// consecutive in `cols` and `map`, so the software pipeline runs through the tile boundaries -- the rows of
+// the next tile's first pair are requested while the last pair of this one is computed, its K and V rows one
+// tile ahead.  At a boundary the sums go to a staging area in LDS and are stored from there in the next
+// iteration, before that iteration's loads are requested: the loop waits for loads only, and a store
+// requested behind them would be waited for as well (the two return through the same counter).  (2) The
+// bias of (query, id) is not staged through LDS: the product Q_chunk x Rel_sel^T leaves bias[query 4g + r][id j]
+// in lane (g, j), register r, and the lane that needs it reads it from there (ds_bpermute), which makes room
+// for the staging area.
+template <int NBC, bool DROP>
+__global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_chain_kernel(const KeyArgs a) {
+    static_assert(NBC == 1 || NBC == 2, "the bias is looked up across the 16 lanes of a group, for up to two chunks of ids");
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int g = lane >> 4, j = lane & 15;
+    const int r8 = lane >> 3, piece = lane & 7;
+    constexpr size_t kRowsBytes = 64 * kRowStride * sizeof(bf16_t), kStageBytes = 16 * kKvOutStride * sizeof(float);
+    bf16_t* q_s = reinterpret_cast<bf16_t*>(smem) + (size_t)wave * 64 * kRowStride;                       // [32 queries][kRowStride]
+    bf16_t* g_s = q_s + 32 * kRowStride;
+    float* o_s = reinterpret_cast<float*>(smem + (size_t)kTileWaves * kRowsBytes) + (size_t)wave * 16 * kKvOutStride;   // [16 keys][64 dK | 64 dV]
+    float2* stat_s = reinterpret_cast<float2*>(smem + (size_t)kTileWaves * (kRowsBytes + kStageBytes)) + (size_t)wave * 32;
+    uint32_t* rowh_s = reinterpret_cast<uint32_t*>(smem + (size_t)kTileWaves * (kRowsBytes + kStageBytes + 32 * sizeof(float2))) +
+                       (size_t)wave * 32;
+    const float qscale = a.scale * kLog2e;
+    const int xcd = blockIdx.x & 7;
+    const int total = a.BH * a.num_tasks, per = (total + 7) >> 3;
+    const int share_begin = xcd * per, share_end = min(total, share_begin + per);
+    const rsrc_t rC = make_rsrc(a.cols, (uint32_t)a.num_chunks * 64u);
+    const rsrc_t rM = make_rsrc(a.map, (uint32_t)a.num_chunks * 512u);
+
+    for (;;) {
+        int item = 0;
+        if (lane == 0) item = atomicAdd(a.queue + xcd * 16, 1);
+        item = __builtin_amdgcn_readfirstlane(item) + share_begin;
+        if (item >= share_end) break;   // every wavefront gets here: the counter only grows from zero
+        const int slab = item / a.num_tasks, task = item - slab * a.num_tasks;
+        const int bh = walk_bh(a.seq_len, slab, a.BH, a.H);
+        const int kt0 = uniform_i32(a.task_tile, task), c0 = uniform_i32(a.task_c0, task), part = uniform_i32(a.task_part, task);
+        const int nch = uniform_i32(a.task_nch, task), ntiles = uniform_i32(a.task_ntiles, task);
+        const int level = uniform_i32(a.tile_info, kt0) & 255;   // the same for all tiles of the task
+        const int len = seq_length_u(a.seq_len, bh / a.H, a.n);
+        const int level_node0 = 2 * a.n - ((2 * a.n) >> level), level_kept = (len + (1 << level) - 1) >> level;
+        const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
+        // the tile at work: its keys, how many the sequence keeps, and the chunk (relative to c0) at which it ends
+        int kt = kt0;
+        int node0 = uniform_i32(a.tile_node0, kt), nkeys = uniform_i32(a.tile_info, kt) >> 8;
+        int kept_keys = level_kept - (node0 - level_node0);
+        if (kept_keys <= 0) continue;   // no key of the first tile exists in this sequence, nor of the ones behind it
+        int tile_end = ntiles > 1 ? uniform_i32(a.chunk_ptr, kt + 1) - c0 : nch;
+        const rsrc_t rQ = make_rsrc(a.Q + base, a.slab_bytes), rG = make_rsrc(a.dout + base, a.slab_bytes);
+        const rsrc_t rK = make_rsrc(a.K + base, a.slab_bytes), rV = make_rsrc(a.V + base, a.slab_bytes);
+        const rsrc_t rS = make_rsrc(a.stat + (int64_t)bh * a.N, (uint32_t)a.N * 8u);
+
+        int node[2][2];
+        uint2 mpn[2];
+        auto load_idx = [&](int c2) {   // a pair past the end repeats the last one (valid addresses, results unused)
+            const int cc = c0 + min(c2, nch - 2);
+#pragma unroll
+            for (int ci = 0; ci < 2; ++ci) {
+                const int at = (cc + ci) * 16;
+                node[ci][0] = buf_i32(rC, (at + r8) * 4);
+                node[ci][1] = buf_i32(rC, (at + 8 + r8) * 4);
+                const u32x2 m2 = __builtin_amdgcn_raw_buffer_load_b64(rM, (at + j) * 32 + 8 * g, 0, 0);
+                mpn[ci] = make_uint2(m2.x, m2.y);
+            }
+        };
+        Row<bf16_t> qa[2][2], ga[2][2];
+        float2 stn[2][2];
+        uint32_t rhn[2][2];
+        const uint32_t bhh = DROP ? drop_bh_hash(a.drop_seed, bh) : 0u;
+        auto load_rows = [&]() {
+#pragma unroll
+            for (int ci = 0; ci < 2; ++ci)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int off = (int)__umul24(node[ci][h], a.row_bytes) + piece * 16;
+                    buf_row(rQ, off, qa[ci][h]);
+                    buf_row(rG, off, ga[ci][h]);
+                    stn[ci][h] = buf_f2(rS, node[ci][h] * 8);
+                    if (DROP) rhn[ci][h] = drop_row_hash(bhh, node[ci][h]);
+                }
+        };
+        // B operands: the keys of a tile (lane j <-> key j) ...
+        Row<bf16_t> kk[2], vv[2], kn[2], vn[2];
+        auto load_keys = [&](int first, int count, Row<bf16_t> (&ko)[2], Row<bf16_t> (&vo)[2]) {
+            const int off = (int)__umul24(first + min(j, count - 1), a.row_bytes) + 32 * g;
+            buf_row(rK, off, ko[0]);
+            buf_row(rK, off + 16, ko[1]);
+            buf_row(rV, off, vo[0]);
+            buf_row(rV, off + 16, vo[1]);
+        };
+        load_idx(0);
+        load_keys(node0, nkeys, kk, vv);
+        // ... and the rows of the table this level can meet
+        bf16x8_t rb[NBC][2];
+#pragma unroll
+        for (int bc = 0; bc < NBC; ++bc) {
+            const int bid = 16 * bc + j;
+            int row = 0;
+            if (bid < a.W)
+                row = level * a.W + bid;                        // (level, order)
+            else if (bid - a.W + 1 < a.num_levels)
+                row = (bid - a.W + 1) * a.W + a.zero;            // r_anc of the ancestor's level
+            const bf16_t* rr = a.rel + (int64_t)row * kD + 16 * g;
+            rb[bc][0] = *reinterpret_cast<const bf16x8_t*>(rr);
+            rb[bc][1] = *reinterpret_cast<const bf16x8_t*>(rr + 8);
+        }
+        load_rows();     // pair 0 (waits for its ids)
+        uint2 mp[2] = {mpn[0], mpn[1]};
+        load_idx(2);     // ids of pair 1
+
+        f32x4_t dk[4], dv[4];
+#pragma unroll
+        for (int f = 0; f < 4; ++f) dk[f] = dv[f] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        // sums of a finished tile wait in o_s for the next iteration: where they go
+        bool staged = false;
+        int st_node0 = 0, st_nkeys = 0;
+        auto store_staged = [&]() {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int idx = lane + 64 * i, key = idx >> 5, q4 = (idx & 31) * 4;
+                if (key < st_nkeys) {
+                    const float4 v = *reinterpret_cast<const float4*>(o_s + key * kKvOutStride + q4);
+                    if (part < 0) {
+                        float* dst = (q4 < kD ? a.dK + q4 : a.dV + (q4 - kD)) + base + (int64_t)(st_node0 + key) * a.sn;
+                        store_once(reinterpret_cast<float4*>(dst), v);
+                    } else {   // the merge kernel reads the partial sums
+                        float* dst = a.part + (((int64_t)bh * a.num_part + part) * 16 + key) * (2 * kD) + q4;
+                        *reinterpret_cast<float4*>(dst) = v;
+                    }
+                }
+            }
+        };
+
+        bool fetch_next_keys = ntiles > 1;   // the next tile's K and V rows are requested with the first pair of this one
+        for (int c2 = 0; c2 < nch; c2 += 2) {
+            wave_lds_sync();  // the previous pair's LDS reads are done
+#pragma unroll
+            for (int ci = 0; ci < 2; ++ci)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int row = 16 * ci + 8 * h + r8;
+                    *reinterpret_cast<uint4*>(q_s + row * kRowStride + piece * 8) = qa[ci][h].w;
+                    *reinterpret_cast<uint4*>(g_s + row * kRowStride + piece * 8) = ga[ci][h].w;
+                    if (piece == 0) stat_s[row] = stn[ci][h];
+                    if (DROP && piece == 0) rowh_s[row] = rhn[ci][h];
+                }
+            __builtin_amdgcn_sched_barrier(0);
+            if (staged) {   // wave-uniform: the tile finished by the previous pair
+                store_staged();
+                staged = false;
+            }
+            // the row registers are free: request the next pair's rows, then the ids of the pair after it
+            const uint2 mpc[2] = {mp[0], mp[1]};
+            load_rows();
+            mp[0] = mpn[0];
+            mp[1] = mpn[1];
+            load_idx(c2 + 4);
+            if (fetch_next_keys) {   // wave-uniform
+                const int nx = kt + 1;
+                load_keys(uniform_i32(a.tile_node0, nx), uniform_i32(a.tile_info, nx) >> 8, kn, vn);
+                fetch_next_keys = false;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            wave_lds_sync();
+            const bool key_kept = j < kept_keys;
+            const bf16x8_t kb0 = __builtin_bit_cast(bf16x8_t, kk[0].w), kb1 = __builtin_bit_cast(bf16x8_t, kk[1].w);
+            const bf16x8_t vb0 = __builtin_bit_cast(bf16x8_t, vv[0].w), vb1 = __builtin_bit_cast(bf16x8_t, vv[1].w);
+            f32x4_t s4[2], d4[2], b4[2][NBC];
+#pragma unroll
+            for (int ci = 0; ci < 2; ++ci) {
+                const bf16_t* qr = q_s + (16 * ci + j) * kRowStride + 16 * g;
+                const bf16_t* gr = g_s + (16 * ci + j) * kRowStride + 16 * g;
+                const bf16x8_t q0 = *reinterpret_cast<const bf16x8_t*>(qr), q1 = *reinterpret_cast<const bf16x8_t*>(qr + 8);
+                const bf16x8_t g0 = *reinterpret_cast<const bf16x8_t*>(gr), g1 = *reinterpret_cast<const bf16x8_t*>(gr + 8);
+                s4[ci] = d4[ci] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                s4[ci] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(q0, kb0, s4[ci], 0, 0, 0);
+                s4[ci] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(q1, kb1, s4[ci], 0, 0, 0);
+                d4[ci] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(g0, vb0, d4[ci], 0, 0, 0);
+                d4[ci] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(g1, vb1, d4[ci], 0, 0, 0);
+#pragma unroll
+                for (int bc = 0; bc < NBC; ++bc) {
+                    b4[ci][bc] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                    b4[ci][bc] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(q0, rb[bc][0], b4[ci][bc], 0, 0, 0);
+                    b4[ci][bc] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(q1, rb[bc][1], b4[ci][bc], 0, 0, 0);
+                }
+            }
+            float ds[2][4], pp[2][4];
+#pragma unroll
+            for (int ci = 0; ci < 2; ++ci) {
+                const float4 x = *reinterpret_cast<const float4*>(stat_s + 16 * ci + 4 * g);
+                const float4 y = *reinterpret_cast<const float4*>(stat_s + 16 * ci + 4 * g + 2);
+                const float2 st[4] = {make_float2(x.x, x.y), make_float2(x.z, x.w), make_float2(y.x, y.y), make_float2(y.z, y.w)};
+                const int bid[4] = {(int)(short)(mpc[ci].x & 0xFFFFu), (int)(short)(mpc[ci].x >> 16),
+                                    (int)(short)(mpc[ci].y & 0xFFFFu), (int)(short)(mpc[ci].y >> 16)};
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    // bias[query 4g + r][id] sits in lane (g, id % 16), register r of the id's chunk
+                    const int src = (lane & 48) | (max(bid[r], 0) & 15);
+                    float bv = __shfl(b4[ci][0][r], src);
+                    if (NBC == 2) {
+                        const float bv1 = __shfl(b4[ci][1][r], src);
+                        bv = bid[r] >= 16 ? bv1 : bv;
+                    }
+                    const float p = bid[r] >= 0 && key_kept ? fast_exp2((s4[ci][r] + bv) * qscale - st[r].x) : 0.f;
+                    if (DROP) {
+                        const uint32_t x2 = bid[r] < a.W ? (uint32_t)(level * a.W + bid[r]) : 0x80000000u + (uint32_t)(node0 + j);
+                        const float keep = drop_scale(rowh_s[16 * ci + 4 * g + r], x2, a.drop_thr, a.drop_inv_keep);
+                        pp[ci][r] = p * keep;
+                        ds[ci][r] = p * (d4[ci][r] * keep - st[r].y);
+                    } else {
+                        pp[ci][r] = p;
+                        ds[ci][r] = p * (d4[ci][r] - st[r].y);
+                    }
+                }
+            }
+            uint32_t shi[4], slo[4], phi[4], plo[4];
+#pragma unroll
+            for (int ci = 0; ci < 2; ++ci) {
+                split_pack(ds[ci][0], ds[ci][1], shi[2 * ci], slo[2 * ci]);
+                split_pack(ds[ci][2], ds[ci][3], shi[2 * ci + 1], slo[2 * ci + 1]);
+                split_pack(pp[ci][0], pp[ci][1], phi[2 * ci], plo[2 * ci]);
+                split_pack(pp[ci][2], pp[ci][3], phi[2 * ci + 1], plo[2 * ci + 1]);
+            }
+            const u32x4 xsh = {shi[0], shi[1], shi[2], shi[3]}, xsl = {slo[0], slo[1], slo[2], slo[3]};
+            const u32x4 xph = {phi[0], phi[1], phi[2], phi[3]}, xpl = {plo[0], plo[1], plo[2], plo[3]};
+            const bf16x8_t sH = __builtin_bit_cast(bf16x8_t, xsh), sL = __builtin_bit_cast(bf16x8_t, xsl);
+            const bf16x8_t pH = __builtin_bit_cast(bf16x8_t, xph), pL = __builtin_bit_cast(bf16x8_t, xpl);
+#pragma unroll
+            for (int f = 0; f < 4; ++f) {
+                const bf16x8_t qB = lds_transposed_b(q_s, kRowStride, f, g, j), gB = lds_transposed_b(g_s, kRowStride, f, g, j);
+                dk[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sH, qB, dk[f], 0, 0, 0);
+                dk[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sL, qB, dk[f], 0, 0, 0);
+                dv[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pH, gB, dv[f], 0, 0, 0);
+                dv[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pL, gB, dv[f], 0, 0, 0);
+            }
+            if (c2 + 2 == tile_end) {   // wave-uniform: the tile is complete
+                // C[m = key][n = feature]: lane holds keys 4g..4g+3, feature 16f + j.  o_s was read (if at all) at
+                // the top of this iteration, before a barrier of the wavefront
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+#pragma unroll
+                    for (int f = 0; f < 4; ++f) {
+                        o_s[(4 * g + r) * kKvOutStride + 16 * f + j] = a.scale * dk[f][r];
+                        o_s[(4 * g + r) * kKvOutStride + kD + 16 * f + j] = dv[f][r];
+                        dk[f][r] = dv[f][r] = 0.f;
+                    }
+                staged = true;
+                st_node0 = node0;
+                st_nkeys = nkeys;
+                if (c2 + 2 < nch) {   // on to the next tile of the task
+                    ++kt;
+                    node0 = uniform_i32(a.tile_node0, kt);
+                    nkeys = uniform_i32(a.tile_info, kt) >> 8;
+                    kept_keys = level_kept - (node0 - level_node0);
+                    tile_end = uniform_i32(a.chunk_ptr, kt + 1) - c0;
+                    kk[0] = kn[0];
+                    kk[1] = kn[1];
+                    vv[0] = vn[0];
+                    vv[1] = vn[1];
+                    fetch_next_keys = kt + 1 < kt0 + ntiles;
+                    if (kept_keys <= 0) break;   // this tile and the ones behind it lie past the end of the sequence
+                }
+            }
+        }
+        wave_lds_sync();
+        if (staged) store_staged();
         wave_lds_sync();
     }
 }

@@ -405,6 +405,7 @@ struct BwdPlan {
     bool q_tiles = false;     // query side of token rows on dense tiles (bwd_q_tile_kernel)
     bool dense_ds = false;    // ... which also forms d_rel (one copy per wavefront): no (w, p) pairs, no d_rel kernel
     bool kv_tiles = false;    // key side on dense tiles of key nodes (bwd_kv_tile_kernel)
+    bool kv_chain = false;    // ... with at most 32 ids per tile: bwd_kv_chain_kernel (tasks that walk several tiles)
     size_t kv_lds = 0;
     int drel_ipw = 32;        // ids per wavefront: 8, 16 or 32
     int drel_block = 32;      // token rows per block
@@ -438,6 +439,12 @@ int plan_bwd(const bpt_graph* g, const bpt_shape_t* s, BwdPlan* p) {
             p->kv_lds = (size_t)kTileWaves * (32 * (g->ktiles.nb_pad + 1) * sizeof(float) + 64 * kRowStride * sizeof(bf16_t) +
                                               32 * sizeof(float2) + 32 * sizeof(uint32_t) + (size_t)parked * 64 * 32);
             p->kv_tiles = p->kv_lds <= lim.lds;
+            const size_t chain_lds = (size_t)kTileWaves * (64 * kRowStride * sizeof(bf16_t) + 16 * kKvOutStride * sizeof(float) +
+                                                            32 * sizeof(float2) + 32 * sizeof(uint32_t));
+            if (g->ktiles.nb_pad <= 32 && chain_lds <= lim.lds) {
+                p->kv_tiles = p->kv_chain = true;
+                p->kv_lds = chain_lds;
+            }
         }
         p->drel_grid_y = p->drel_tile ? 1 : (p->drel_rows + kRgIds - 1) / kRgIds;
         blocks = (int64_t)s->B * s->H * ((g->n + kRgRows - 1) / kRgRows);
@@ -600,6 +607,21 @@ template <int NBC>
 int launch_kv_tiles(const KeyArgs& t, const BwdPlan& p, const DeviceLimits& lim, hipStream_t st) {
     return t.drop_thr ? launch_kv_tiles_as<NBC, true>(t, p, lim, st) : launch_kv_tiles_as<NBC, false>(t, p, lim, st);
 }
+template <int NBC, bool DROP>
+int launch_kv_chain_as(const KeyArgs& t, const BwdPlan& p, const DeviceLimits& lim, hipStream_t st) {
+    if (p.kv_lds > 65536)
+        BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_kv_chain_kernel<NBC, DROP>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.kv_lds));
+    const int grid =
+        std::max(8, lim.cus * resident_blocks(bwd_kv_chain_kernel<NBC, DROP>, kTileThreads, p.kv_lds, lim) / 8 * 8);
+    BPT_LAUNCH("bwd_kv_chain_kernel", (bwd_kv_chain_kernel<NBC, DROP>), dim3(grid), dim3(kTileThreads), p.kv_lds, st, t);
+    BPT_HIP(hipGetLastError());
+    return BPT_OK;
+}
+template <int NBC>
+int launch_kv_chain(const KeyArgs& t, const BwdPlan& p, const DeviceLimits& lim, hipStream_t st) {
+    return t.drop_thr ? launch_kv_chain_as<NBC, true>(t, p, lim, st) : launch_kv_chain_as<NBC, false>(t, p, lim, st);
+}
 
 // bf16 key side on dense tiles of key nodes
 // queue_cleared: the query side ran in the same call and its last kernel has put the task counters to zero
@@ -633,6 +655,8 @@ int run_bwd_kv_tiles(const bpt_graph* g, const BwdPlan& p, const AttnArgs& a, co
     t.task_c0 = kt.task_c0;
     t.task_nch = kt.task_nch;
     t.task_part = kt.task_part;
+    t.task_ntiles = kt.task_ntiles;
+    t.chunk_ptr = kt.chunk_ptr;
     t.map = kt.map;
     t.num_tasks = kt.num_tasks;
     t.num_part = kt.num_part;
@@ -653,8 +677,8 @@ int run_bwd_kv_tiles(const bpt_graph* g, const BwdPlan& p, const AttnArgs& a, co
     }
     int rc = BPT_ERR_UNSUPPORTED;
     switch (kt.nb_pad / 16) {
-        case 1: rc = launch_kv_tiles<1>(t, p, lim, st); break;
-        case 2: rc = launch_kv_tiles<2>(t, p, lim, st); break;
+        case 1: rc = p.kv_chain ? launch_kv_chain<1>(t, p, lim, st) : launch_kv_tiles<1>(t, p, lim, st); break;
+        case 2: rc = p.kv_chain ? launch_kv_chain<2>(t, p, lim, st) : launch_kv_tiles<2>(t, p, lim, st); break;
         case 3: rc = launch_kv_tiles<3>(t, p, lim, st); break;
         case 4: rc = launch_kv_tiles<4>(t, p, lim, st); break;
         case 5: rc = launch_kv_tiles<5>(t, p, lim, st); break;

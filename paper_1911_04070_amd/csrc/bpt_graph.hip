@@ -485,6 +485,7 @@ void free_key_tiles(KeyTiles& t) {
     (void)hipFree(t.task_c0);
     (void)hipFree(t.task_nch);
     (void)hipFree(t.task_part);
+    (void)hipFree(t.task_ntiles);
     (void)hipFree(t.multi_tile);
     (void)hipFree(t.multi_ptr);
     t = KeyTiles();

@@ -50,7 +50,10 @@ struct TokenTiles {
 // of them (tokens on either side, and for token keys their ancestor spans), in
 // ascending node id, in chunks of 16 (an even number per tile).  A tile's chunk list
 // is cut into tasks of at most key_task_chunks(n) chunks; tiles with several tasks are
-// summed by a merge kernel in task order.  Longer tasks mean fewer partial sums to write and
+// summed by a merge kernel in task order.  Tiles with few chunks (the fine levels: a key of level l is read
+// by about (k + 1) 2^l tokens) are chained instead: one task walks several consecutive tiles of a level, so
+// that the software pipeline of the kernel runs through them instead of starting up for every tile.
+// Longer tasks mean fewer partial sums to write and
 // merge (n = 65536: key side 0.67 -> 0.60 ms) but, when a (batch, head) has few tiles, waves
 // that wait for the one with the longest task (n = 512: 0.12 -> 0.29 ms).
 inline int key_task_chunks(int n) { return n >= 16384 ? 64 : 32; }
@@ -68,6 +71,7 @@ struct KeyTiles {
     int32_t* task_c0 = nullptr;     // [tasks] first chunk
     int32_t* task_nch = nullptr;    // [tasks] chunks (even)
     int32_t* task_part = nullptr;   // [tasks] partial slot, or -1 if the tile has one task
+    int32_t* task_ntiles = nullptr; // [tasks] consecutive tiles of one level the task walks (1 unless chained)
     int32_t* multi_tile = nullptr;  // [num_multi] tiles with several tasks
     int32_t* multi_ptr = nullptr;   // [num_multi+1] their partial slots
 };

@@ -17,6 +17,7 @@ constexpr int kScanBlock = kTB * kScanItems;   // elements per block of the scan
 constexpr int kMaxLevels = 24;                 // n <= 2^22
 constexpr int kMaxSortedTasks = 1 << 16;       // key-tile tasks are put in stretch order up to this many (the ordering is quadratic)
 constexpr int kMaxBuckets = 2 * kMaxLevels;
+constexpr int kChainChunks = 8;                // key tiles of at most this many chunks are chained
 
 __host__ __device__ inline int level_off(int n, int level) { return 2 * n - ((2 * n) >> level); }
 
@@ -208,6 +209,7 @@ __global__ void token_tile_map(int n, int nb, int W, int zero, const int32_t* __
 // ---- key tiles -----------------------------------------------------------------------------
 struct LevelBases {
     int32_t tile_base[kMaxLevels + 1];   // first tile of every level that has contextual edges
+    int32_t chain[kMaxLevels];           // tiles of the level that one task walks (1: every tile has its own tasks)
 };
 
 // One thread per key tile: level, keys, the range of tokens that attend to it in each bucket
@@ -261,7 +263,9 @@ __global__ void key_tile_layout(int n, int num_levels, int ctx_levels, int nkt, 
     int nch = (total + 15) / 16;
     nch += nch & 1;
     knch[kt] = nch;
-    const int nt = max(1, (nch + task_chunks - 1) / task_chunks);
+    int nt = max(1, (nch + task_chunks - 1) / task_chunks);
+    // a chained level: the first tile of every group of lb.chain[l] carries the group's one task
+    if (lb.chain[l] > 1) nt = (kt - lb.tile_base[l]) % lb.chain[l] == 0 ? 1 : 0;
     ntask[kt] = nt;
     npart[kt] = nt > 1 ? nt : 0;
     is_multi[kt] = nt > 1 ? 1 : 0;
@@ -340,22 +344,36 @@ __global__ void key_tile_map_ancestors(int num_levels, int W, int token_tiles, c
 }
 
 // one thread per key tile: its tasks; tiles with several tasks also enter the merge list
-__global__ void key_tile_tasks(int nkt, int task_chunks, int num_multi, int num_part,
+__global__ void key_tile_tasks(int nkt, int ctx_levels, LevelBases lb, int task_chunks, int num_multi, int num_part,
                                const int32_t* __restrict__ kchunk_ptr, const int32_t* __restrict__ ntask,
                                const int32_t* __restrict__ task_ptr, const int32_t* __restrict__ part_base,
                                const int32_t* __restrict__ multi_idx, int32_t* __restrict__ task_tile,
                                int32_t* __restrict__ task_c0, int32_t* __restrict__ task_nch,
-                               int32_t* __restrict__ task_part, int32_t* __restrict__ multi_tile,
-                               int32_t* __restrict__ multi_ptr) {
+                               int32_t* __restrict__ task_part, int32_t* __restrict__ task_ntiles,
+                               int32_t* __restrict__ multi_tile, int32_t* __restrict__ multi_ptr) {
     const int kt = blockIdx.x * blockDim.x + threadIdx.x;
     if (kt == 0) multi_ptr[num_multi] = num_part;
     if (kt >= nkt) return;
     const int c0 = kchunk_ptr[kt], nch = kchunk_ptr[kt + 1] - c0, nt = ntask[kt], tp = task_ptr[kt];
+    int l = 0;
+    while (l + 1 < ctx_levels && lb.tile_base[l + 1] <= kt) ++l;
+    if (lb.chain[l] > 1) {   // one task for this tile and the following ones of its group (their chunks are consecutive)
+        if (nt == 1) {
+            const int last = min(kt + lb.chain[l], lb.tile_base[l + 1]);
+            task_tile[tp] = kt;
+            task_c0[tp] = c0;
+            task_nch[tp] = kchunk_ptr[last] - c0;
+            task_part[tp] = -1;
+            task_ntiles[tp] = last - kt;
+        }
+        return;
+    }
     for (int t = 0; t < nt; ++t) {
         task_tile[tp + t] = kt;
         task_c0[tp + t] = c0 + t * task_chunks;
         task_nch[tp + t] = max(0, min(task_chunks, nch - t * task_chunks));
         task_part[tp + t] = nt > 1 ? part_base[kt] + t : -1;
+        task_ntiles[tp + t] = 1;
     }
     if (nt > 1) {
         multi_tile[multi_idx[kt]] = kt;
@@ -376,8 +394,9 @@ constexpr int kSegTokens = 512;
 __global__ void key_tile_task_order(int num_tasks, int n, const int32_t* __restrict__ cols,
                                     const int32_t* __restrict__ in_tile, const int32_t* __restrict__ in_c0,
                                     const int32_t* __restrict__ in_nch, const int32_t* __restrict__ in_part,
-                                    int32_t* __restrict__ task_tile, int32_t* __restrict__ task_c0,
-                                    int32_t* __restrict__ task_nch, int32_t* __restrict__ task_part) {
+                                    const int32_t* __restrict__ in_ntiles, int32_t* __restrict__ task_tile,
+                                    int32_t* __restrict__ task_c0, int32_t* __restrict__ task_nch,
+                                    int32_t* __restrict__ task_part, int32_t* __restrict__ task_ntiles) {
     __shared__ int32_t keys_s[kTB];
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
     // sort key: stretch ascending, then chunks descending (at most 2^12 chunks per task); a list that
@@ -403,6 +422,7 @@ __global__ void key_tile_task_order(int num_tasks, int n, const int32_t* __restr
         task_c0[rank] = in_c0[t];
         task_nch[rank] = in_nch[t];
         task_part[rank] = in_part[t];
+        task_ntiles[rank] = in_ntiles[t];
     }
 }
 
@@ -429,9 +449,18 @@ int build_tile_metadata(bpt_graph* g, const int32_t* cnt_l, const int32_t* min_l
 
     LevelBases lb = {};
     for (int l = 0; l < ctx_levels; ++l) lb.tile_base[l + 1] = lb.tile_base[l] + ((n >> l) + 15) / 16;
+    const int task_chunks = key_task_chunks(n);
+    for (int l = 0; l < ctx_levels; ++l) {
+        // an upper bound of a tile's columns: the tokens that read its 16 keys from either side (a key of level l
+        // is read by at most (k + 2) 2^l tokens on a side, the ranges of consecutive keys are 2^l apart), and for
+        // token keys their ancestors; tiles of at most kChainChunks chunks are chained up to a task's length
+        const int64_t cols = (int64_t)(g->causal ? 1 : 2) * (17 + g->k) * ((int64_t)1 << l) + (l == 0 ? 28 + num_levels : 0);
+        const int64_t nch = ((cols + 15) / 16 + 1) & ~(int64_t)1;
+        // (the chained kernel looks the bias up across lanes, which covers 32 ids)
+        lb.chain[l] = nch <= kChainChunks && ((W + num_levels - 1 + 15) & ~15) <= 32 ? (int)std::max<int64_t>(1, task_chunks / nch) : 1;
+    }
     const int nkt = lb.tile_base[ctx_levels];
     const bool want_keys = W + num_levels <= 32767;
-    const int task_chunks = key_task_chunks(n);
 
     // ---- phase 1: everything whose size is known in advance ----
     DeviceBuf used, pos, sums, totals, tile_lo, tile_hi, tile_first, tile_nch;
@@ -517,6 +546,7 @@ int build_tile_metadata(bpt_graph* g, const int32_t* cnt_l, const int32_t* min_l
         if ((rc = device_alloc(&kt.cols, (size_t)kchunks * 16)) || (rc = device_alloc(&kt.map, (size_t)kchunks * 256)) ||
             (rc = device_alloc(&kt.task_tile, num_tasks)) || (rc = device_alloc(&kt.task_c0, num_tasks)) ||
             (rc = device_alloc(&kt.task_nch, num_tasks)) || (rc = device_alloc(&kt.task_part, num_tasks)) ||
+            (rc = device_alloc(&kt.task_ntiles, num_tasks)) ||
             (rc = device_alloc(&kt.multi_tile, num_multi)) || (rc = device_alloc(&kt.multi_ptr, (size_t)num_multi + 1)))
             return rc;
         BPT_HIP(hipMemsetAsync(kt.map, 0xFF, sizeof(int16_t) * (size_t)kchunks * 256, st));
@@ -528,23 +558,25 @@ int build_tile_metadata(bpt_graph* g, const int32_t* cnt_l, const int32_t* min_l
         hipLaunchKernelGGL(key_tile_map_ancestors, dim3((token_tiles * 16 + kTB - 1) / kTB), dim3(kTB), 0, st, num_levels, W,
                            token_tiles, kt.chunk_ptr, kt.tile_node0, kt.tile_info, anc_first.as<int32_t>(), kt.map);
         const bool reorder = n > kSegTokens && num_tasks <= kMaxSortedTasks;
-        DeviceBuf ut_tile, ut_c0, ut_nch, ut_part;   // the tasks in tile order, when they are put in another one
+        DeviceBuf ut_tile, ut_c0, ut_nch, ut_part, ut_ntiles;   // the tasks in tile order, when they are put in another one
         if (reorder) {
             const size_t tbytes = sizeof(int32_t) * (size_t)std::max(num_tasks, 1);
             BPT_HIP(ut_tile.alloc(tbytes));
             BPT_HIP(ut_c0.alloc(tbytes));
             BPT_HIP(ut_nch.alloc(tbytes));
             BPT_HIP(ut_part.alloc(tbytes));
+            BPT_HIP(ut_ntiles.alloc(tbytes));
         }
-        hipLaunchKernelGGL(key_tile_tasks, dim3((nkt + kTB - 1) / kTB), dim3(kTB), 0, st, nkt, task_chunks, num_multi,
-                           num_part, kt.chunk_ptr, ntask.as<int32_t>(), task_ptr.as<int32_t>(), part_base.as<int32_t>(),
-                           multi_idx.as<int32_t>(), reorder ? ut_tile.as<int32_t>() : kt.task_tile,
+        hipLaunchKernelGGL(key_tile_tasks, dim3((nkt + kTB - 1) / kTB), dim3(kTB), 0, st, nkt, ctx_levels, lb, task_chunks,
+                           num_multi, num_part, kt.chunk_ptr, ntask.as<int32_t>(), task_ptr.as<int32_t>(),
+                           part_base.as<int32_t>(), multi_idx.as<int32_t>(), reorder ? ut_tile.as<int32_t>() : kt.task_tile,
                            reorder ? ut_c0.as<int32_t>() : kt.task_c0, reorder ? ut_nch.as<int32_t>() : kt.task_nch,
-                           reorder ? ut_part.as<int32_t>() : kt.task_part, kt.multi_tile, kt.multi_ptr);
+                           reorder ? ut_part.as<int32_t>() : kt.task_part, reorder ? ut_ntiles.as<int32_t>() : kt.task_ntiles,
+                           kt.multi_tile, kt.multi_ptr);
         if (reorder && num_tasks > 0)
             hipLaunchKernelGGL(key_tile_task_order, dim3((num_tasks + kTB - 1) / kTB), dim3(kTB), 0, st, num_tasks, n, kt.cols,
                                ut_tile.as<int32_t>(), ut_c0.as<int32_t>(), ut_nch.as<int32_t>(), ut_part.as<int32_t>(),
-                               kt.task_tile, kt.task_c0, kt.task_nch, kt.task_part);
+                               ut_ntiles.as<int32_t>(), kt.task_tile, kt.task_c0, kt.task_nch, kt.task_part, kt.task_ntiles);
         BPT_HIP(hipGetLastError());
         if (reorder) BPT_HIP(hipStreamSynchronize(st));   // the lists in tile order are freed at the end of this block
         kt.num_chunks = (int32_t)kchunks;

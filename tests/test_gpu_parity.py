@@ -440,7 +440,8 @@ def test_large_table_on_every_kernel_variant(n, k, causal, B, H, q_times, rel_st
     torch.cuda.synchronize()
     ran = set(bpt.bpt_profile_report())
     bpt.bpt_profile_enable(False)
-    assert {"fwd_tile_kernel", "bwd_q_tile_kernel", "bwd_kv_tile_kernel"} <= ran, ran   # the matrix-core path
+    assert {"fwd_tile_kernel", "bwd_q_tile_kernel"} <= ran, ran   # the matrix-core path
+    assert ran & {"bwd_kv_tile_kernel", "bwd_kv_chain_kernel"}, ran
     assert ("rel_grad_tile_kernel" in ran) == hand_over, ran
     o, l, _ = oracle.attn_fwd_lengths(n, k, causal, lens, x["Q"], x["K"], x["V"], x["Rel"], w.scale, dropout=p, seed=seed)
     refs = oracle.attn_bwd_lengths(n, k, causal, lens, x["Q"], x["K"], x["V"], x["Rel"], x["dO"], w.scale, dropout=p,
