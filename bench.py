@@ -82,6 +82,9 @@ def parse():
     ap.add_argument("--calibrate-gather-mib", type=int, default=0,
                     help="only run the library's calibration gather over this many MiB of 128-byte rows (10 times) and "
                          "exit: known traffic of the attention kernels' request shape for scaling the same counters")
+    ap.add_argument("--zero-unkept", action="store_true",
+                    help="workloads with sequences of different lengths: zero-fill the rows of nodes a sequence does not "
+                         "keep (the default leaves them unwritten, bpt_shape_t.leave_unkept)")
     ap.add_argument("--regions", type=int, default=5,
                     help="the timed steps are run as this many back-to-back regions (each synchronised on both sides); "
                          "ms_per_step is the median region, the spread is reported beside it")
@@ -286,12 +289,14 @@ def main():
     ws_b = torch.empty(max(bws, 256), dtype=torch.uint8, device="cuda")
 
     drop = (args.dropout, 1911) if args.dropout > 0 else None
+    leave = lengths is not None and not args.zero_unkept
 
     def step():
-        bpt.bpt_attn_fwd(g, Q, K, V, R, scale=w.scale, out=out, lse=lse, workspace=ws_f, seq_len=lens_d, dropout=drop)
+        bpt.bpt_attn_fwd(g, Q, K, V, R, scale=w.scale, out=out, lse=lse, workspace=ws_f, seq_len=lens_d, dropout=drop,
+                         leave_unkept=leave)
         if w.backward:
             bpt.bpt_attn_bwd(g, Q, K, V, R, lse, dO, scale=w.scale, grads=grads, workspace=ws_b, seq_len=lens_d,
-                             dropout=drop)
+                             dropout=drop, leave_unkept=leave)
 
     for _ in range(args.warmup):
         step()
@@ -321,15 +326,15 @@ def main():
         return float(np.mean([a.elapsed_time(b) for a, b in evs]))
 
     reps = max(5, min(args.steps, 30))
-    stage_ms = {"fwd": timed(lambda: bpt.bpt_attn_fwd(g, Q, K, V, R, scale=w.scale, out=out, lse=lse,
-                                                      workspace=ws_f, seq_len=lens_d, dropout=drop), reps)}
+    stage_ms = {"fwd": timed(lambda: bpt.bpt_attn_fwd(g, Q, K, V, R, scale=w.scale, out=out, lse=lse, workspace=ws_f,
+                                                      seq_len=lens_d, dropout=drop, leave_unkept=leave), reps)}
     if w.backward:
         stage_ms["bwd_query_side"] = timed(
             lambda: bpt.bpt_attn_bwd_query_side(g, Q, K, V, R, lse, dO, grads[0], grads[3], ws_b, scale=w.scale,
-                                                seq_len=lens_d, dropout=drop), reps)
+                                                seq_len=lens_d, dropout=drop, leave_unkept=leave), reps)
         stage_ms["bwd_key_side"] = timed(
             lambda: bpt.bpt_attn_bwd_key_side(g, Q, K, V, R, lse, dO, grads[1], grads[2], ws_b, scale=w.scale,
-                                              seq_len=lens_d, dropout=drop), reps)
+                                              seq_len=lens_d, dropout=drop, leave_unkept=leave), reps)
 
     # per-kernel device time, live: the library brackets each of its launches with HIP events on the launch stream
     bpt.bpt_profile_enable(True)
@@ -502,7 +507,7 @@ def main():
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "n": w.n, "k": w.k, "causal": w.causal, "batch": w.B, "heads": w.H,
                    "head_dim": w.D, "nodes": g.num_nodes, "edges": g.num_edges, "edge_instances": edge_inst,
-                   "backward": w.backward, "dropout": args.dropout,
+                   "backward": w.backward, "dropout": args.dropout, "unkept_rows": ("unwritten" if leave else "zero-filled") if lengths is not None else None,
                    "lengths": ([int(v) for v in lengths] if lengths is not None else None)},
         "graph_build_ms": round(build_ms, 3),
         "edges_per_s_incl_build": round(edge_inst / ((ms_per_step + build_ms) * 1e-3), 1),

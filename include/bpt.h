@@ -50,9 +50,9 @@
  * its first ceil(len / 2^l) nodes, the last one possibly cut short.  An edge of the
  * graph counts iff both of its nodes are kept; this is what Algorithm 1 gives when its
  * runs are clipped to the kept nodes of each level.  Rows of nodes that are not kept
- * produce zeros in every output (out, lse, dQ, dK, dV) and add nothing to d_rel; their
- * input rows are never used but must hold finite values.  Values of seq_len outside
- * [0, n] are clamped.
+ * produce zeros in every output (out, lse, dQ, dK, dV) -- or are left unwritten, see
+ * bpt_shape_t.leave_unkept -- and add nothing to d_rel; their input rows are never used but
+ * must hold finite values.  Values of seq_len outside [0, n] are clamped.
  */
 #ifndef BPT_H_
 #define BPT_H_
@@ -89,6 +89,10 @@ typedef struct {
                               tokens.  See "Sequences shorter than n" above. */
     float dropout_p;     /* dropout rate on the attention weights, 0 <= p < 1; 0: none.  See below. */
     uint32_t dropout_seed;
+    int32_t leave_unkept; /* with seq_len, nonzero: the rows of out, lse, dQ, dK, dV of nodes that a sequence does
+                             not keep are left unwritten (they hold whatever the buffers held) instead of being
+                             zero-filled, so that the time and the bytes written follow the tokens that exist
+                             rather than the padded size.  Rows of kept nodes and d_rel are the same either way. */
 } bpt_shape_t;
 
 /* Sec. 3.2 + Algorithm 1.  Builds, on the current device, the graph of a

@@ -34,7 +34,7 @@ class BptShape(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("D", ctypes.c_int32), ("dtype", ctypes.c_int32),
                 ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64), ("stride_n", ctypes.c_int64),
                 ("scale", ctypes.c_float), ("seq_len", ctypes.c_void_p), ("dropout_p", ctypes.c_float),
-                ("dropout_seed", ctypes.c_uint32)]
+                ("dropout_seed", ctypes.c_uint32), ("leave_unkept", ctypes.c_int32)]
 
 
 class BptLayerParams(ctypes.Structure):
@@ -215,7 +215,7 @@ def bpt_build_graph(n: int, k: int, causal: bool) -> Graph:
 
 
 def _shape_of(g: Graph, x: torch.Tensor, scale: Optional[float], seq_len: Optional[torch.Tensor] = None,
-              dropout: Optional[Tuple[float, int]] = None) -> BptShape:
+              dropout: Optional[Tuple[float, int]] = None, leave_unkept: bool = False) -> BptShape:
     if x.dim() != 4 or x.shape[2] != g.num_nodes:
         raise ValueError("expected a [B,H,N=%d,D] tensor, got %s" % (g.num_nodes, tuple(x.shape)))
     if x.stride(3) != 1:
@@ -234,7 +234,8 @@ def _shape_of(g: Graph, x: torch.Tensor, scale: Optional[float], seq_len: Option
             raise ValueError("seq_len must be a contiguous int32 tensor of B entries on the tensors' device")
         lens = seq_len.data_ptr()
     return BptShape(B, H, D, dt, x.stride(0), x.stride(1), x.stride(2), float(scale) if scale else 0.0, lens,
-                    float(dropout[0]) if dropout else 0.0, (int(dropout[1]) & 0xFFFFFFFF) if dropout else 0)
+                    float(dropout[0]) if dropout else 0.0, (int(dropout[1]) & 0xFFFFFFFF) if dropout else 0,
+                    1 if leave_unkept else 0)
 
 
 def _same_layout(ref: torch.Tensor, *others: torch.Tensor) -> None:
@@ -262,12 +263,12 @@ def _workspace(nbytes: int, device) -> Tuple[Optional[torch.Tensor], int]:
 def bpt_attn_fwd(g: Graph, Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, rel: torch.Tensor,
                  scale: Optional[float] = None, out: Optional[torch.Tensor] = None,
                  lse: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
-                 seq_len: Optional[torch.Tensor] = None, dropout: Optional[Tuple[float, int]] = None):
+                 seq_len: Optional[torch.Tensor] = None, dropout: Optional[Tuple[float, int]] = None, leave_unkept: bool = False):
     """out, lse = graph attention of eq. (8).  Q,K,V: [B,H,N,D] cuda tensors; rel: [levels,W,D];
     seq_len: optional int32 [B] token counts of sequences shorter than n; dropout: (rate, seed) of the dropout on
     the attention weights."""
     L = load_library()
-    shp = _shape_of(g, Q, scale, seq_len, dropout)
+    shp = _shape_of(g, Q, scale, seq_len, dropout, leave_unkept)
     _same_layout(Q, K, V)
     if K.dtype != Q.dtype or V.dtype != Q.dtype or rel.dtype != Q.dtype:
         raise ValueError("Q, K, V and rel must share a dtype")
@@ -291,11 +292,11 @@ def bpt_attn_fwd(g: Graph, Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, re
 
 def bpt_attn_fwd_static(g: Graph, Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, rel: torch.Tensor,
                         out: torch.Tensor, lse: torch.Tensor, scale: Optional[float] = None,
-                        seq_len: Optional[torch.Tensor] = None, dropout: Optional[Tuple[float, int]] = None):
+                        seq_len: Optional[torch.Tensor] = None, dropout: Optional[Tuple[float, int]] = None, leave_unkept: bool = False):
     """bpt_attn_fwd into caller-provided out and lse with the library's static scratch: this wrapper and the call
     allocate nothing."""
     L = load_library()
-    shp = _shape_of(g, Q, scale, seq_len, dropout)
+    shp = _shape_of(g, Q, scale, seq_len, dropout, leave_unkept)
     _same_layout(Q, K, V, out)
     if K.dtype != Q.dtype or V.dtype != Q.dtype or rel.dtype != Q.dtype or out.dtype != Q.dtype:
         raise ValueError("Q, K, V, rel and out must share a dtype")
@@ -342,9 +343,9 @@ def _check_bwd_workspace(L, g, shp, workspace) -> int:
     return ws_bytes
 
 
-def _bwd_prepare(g, Q, K, V, rel, lse, dout, scale, grads, workspace, seq_len=None, dropout=None):
+def _bwd_prepare(g, Q, K, V, rel, lse, dout, scale, grads, workspace, seq_len=None, dropout=None, leave_unkept=False):
     L = load_library()
-    shp = _shape_of(g, Q, scale, seq_len, dropout)
+    shp = _shape_of(g, Q, scale, seq_len, dropout, leave_unkept)
     _check_bwd_inputs(g, shp, Q, K, V, rel, lse, dout)
     if grads is None:
         dQ, dK, dV = (torch.empty_strided(Q.shape, Q.stride(), dtype=torch.float32, device=Q.device)
@@ -363,10 +364,10 @@ def _bwd_prepare(g, Q, K, V, rel, lse, dout, scale, grads, workspace, seq_len=No
 
 def bpt_attn_bwd(g: Graph, Q, K, V, rel, lse, dout, scale: Optional[float] = None,
                  grads: Optional[Tuple[torch.Tensor, ...]] = None, workspace: Optional[torch.Tensor] = None,
-                 seq_len: Optional[torch.Tensor] = None, dropout: Optional[Tuple[float, int]] = None):
+                 seq_len: Optional[torch.Tensor] = None, dropout: Optional[Tuple[float, int]] = None, leave_unkept: bool = False):
     """dQ, dK, dV, d_rel (all fp32) = gradient of eq. (8) given dout and the forward's lse (and its dropout)."""
     L, shp, (dQ, dK, dV, d_rel), ws, ws_bytes = _bwd_prepare(g, Q, K, V, rel, lse, dout, scale, grads, workspace,
-                                                             seq_len, dropout)
+                                                             seq_len, dropout, leave_unkept)
     _check(L.bpt_attn_bwd(g.handle, ctypes.byref(shp), Q.data_ptr(), K.data_ptr(), V.data_ptr(), rel.data_ptr(),
                           lse.data_ptr(), dout.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(),
                           d_rel.data_ptr(), ws.data_ptr(), ws_bytes, _stream_ptr()), "bpt_attn_bwd")
@@ -375,10 +376,10 @@ def bpt_attn_bwd(g: Graph, Q, K, V, rel, lse, dout, scale: Optional[float] = Non
 
 def bpt_attn_bwd_query_side(g: Graph, Q, K, V, rel, lse, dout, dQ, d_rel, workspace,
                             scale: Optional[float] = None, seq_len: Optional[torch.Tensor] = None,
-                            dropout: Optional[Tuple[float, int]] = None):
+                            dropout: Optional[Tuple[float, int]] = None, leave_unkept: bool = False):
     """First stage of the backward: dQ, d_rel, and delta into the workspace."""
     L = load_library()
-    shp = _shape_of(g, Q, scale, seq_len, dropout)
+    shp = _shape_of(g, Q, scale, seq_len, dropout, leave_unkept)
     _check_bwd_inputs(g, shp, Q, K, V, rel, lse, dout)
     _check_grad(Q, dQ)
     _check_d_rel(g, shp, Q, d_rel)
@@ -391,10 +392,10 @@ def bpt_attn_bwd_query_side(g: Graph, Q, K, V, rel, lse, dout, dQ, d_rel, worksp
 
 
 def bpt_attn_bwd_key_side(g: Graph, Q, K, V, rel, lse, dout, dK, dV, workspace, scale: Optional[float] = None,
-                          seq_len: Optional[torch.Tensor] = None, dropout: Optional[Tuple[float, int]] = None):
+                          seq_len: Optional[torch.Tensor] = None, dropout: Optional[Tuple[float, int]] = None, leave_unkept: bool = False):
     """Second stage of the backward: dK, dV (reads delta from the workspace)."""
     L = load_library()
-    shp = _shape_of(g, Q, scale, seq_len, dropout)
+    shp = _shape_of(g, Q, scale, seq_len, dropout, leave_unkept)
     _check_bwd_inputs(g, shp, Q, K, V, rel, lse, dout)
     _check_grad(Q, dK, dV)
     _check_bwd_workspace(L, g, shp, workspace)

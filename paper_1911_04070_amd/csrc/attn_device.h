@@ -43,6 +43,7 @@ struct AttnArgs {
     int32_t drel_block;     // token rows per block of rel_grad_kernel
     int32_t rel_rows;       // rows of the whole table
     const int32_t* seq_len; // [B] tokens of every sequence, or null: all have n_tokens
+    int32_t leave_unkept;   // with seq_len: rows of nodes a sequence does not keep are left unwritten, not zero-filled
     int32_t lg;             // log2(n_tokens)
     // dropout on the attention weights: an edge is kept iff its hash >= drop_thr (0: no dropout)
     uint32_t drop_thr, drop_seed;

@@ -36,6 +36,7 @@ struct KeyArgs {
     const int16_t* map;
     int32_t num_tasks, num_part, num_chunks, nb_pad, W, zero;
     const int32_t* seq_len;   // [B] tokens of every sequence, or null
+    int32_t leave_unkept;     // rows of nodes a shorter sequence does not keep: left unwritten instead of zero-filled
     int32_t n;
     uint32_t drop_thr, drop_seed;   // dropout on the attention weights (DROP variants)
     float drop_inv_keep;
@@ -621,15 +622,17 @@ __global__ void __launch_bounds__(256) kv_tile_merge_kernel(const KeyArgs a, con
         // does not keep (which the tile kernel steps over).  A wavefront looks at 64 consecutive nodes, one
         // per lane, and then writes the rows found two at a time: 16 lanes x 16 bytes for each of dK and dV
         // of a row.
-        const int row0 = a.seq_len ? 0 : (first_zero & ~63), waves_per_bh = (a.N - row0 + 63) >> 6;
+        const int row0 = a.seq_len && !a.leave_unkept ? 0 : (first_zero & ~63), waves_per_bh = (a.N - row0 + 63) >> 6;
         const int64_t gw = ((int64_t)(blockIdx.x - merge_blocks) * blockDim.x + threadIdx.x) >> 6;
         if (gw >= (int64_t)a.BH * waves_per_bh) return;
         const int lane = threadIdx.x & 63;
         const int bh = (int)(gw / waves_per_bh), first = row0 + 64 * (int)(gw - (int64_t)bh * waves_per_bh);
         const int row = first + lane;
         bool gone = row < a.N && row >= first_zero;
-        if (a.seq_len && row < a.N)
-            gone = gone || node_first_token(row, 31 - __clz(a.n)) >= seq_length(a.seq_len, bh / a.H, a.n);
+        if (a.seq_len && row < a.N) {
+            const bool unkept = node_first_token(row, 31 - __clz(a.n)) >= seq_length(a.seq_len, bh / a.H, a.n);
+            gone = a.leave_unkept ? gone && !unkept : gone || unkept;
+        }
         uint64_t todo = __ballot(gone);
         const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
         while (todo) {   // wave-uniform
@@ -652,6 +655,7 @@ __global__ void __launch_bounds__(256) kv_tile_merge_kernel(const KeyArgs a, con
     // a tile none of whose keys exists in this (shorter) sequence has no partial sums: zeros
     const int len = seq_length(a.seq_len, bh / a.H, a.n);
     const bool gone = ((len + (1 << level) - 1) >> level) - (node0 - (2 * a.n - ((2 * a.n) >> level))) <= 0;
+    if (gone && a.leave_unkept) return;   // uniform for the workgroup
     // thread -> (key, 4 consecutive values of its 64 dK | 64 dV); four partial sums in flight, combined in a fixed order
     const int p0 = gone ? multi_ptr[mt + 1] : multi_ptr[mt], p1 = multi_ptr[mt + 1];
     for (int i = threadIdx.x; i < nkeys * 32; i += blockDim.x) {

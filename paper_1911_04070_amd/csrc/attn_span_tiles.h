@@ -35,6 +35,7 @@ struct SpanArgs {
     int32_t BH, H, N, n, L, W, zero;
     float scale;
     const int32_t* seq_len;   // [B] tokens of every sequence, or null
+    int32_t leave_unkept;     // rows of nodes a shorter sequence does not keep: left unwritten instead of zero-filled
     uint32_t drop_thr, drop_seed;   // dropout on the attention weights (DROP variants)
     float drop_inv_keep;
 };
@@ -75,28 +76,25 @@ __device__ __forceinline__ float span_shift(const SpanArgs& a, int level, int g,
 }
 
 // A block of 32 tokens past the end of a shorter sequence: nothing is read; its spans inside the
-// block get zero rows (forward: out, lse; backward: dQ, and a `stat` entry that switches the row
-// off on the key side) and its ancestors an empty partial (forward: no weight; backward: zero sums).
+// block get zero rows (forward: out, lse; backward: dQ) unless such rows are left unwritten, and in the
+// backward a `stat` entry that switches the row off on the key side.  Its ancestors get nothing from
+// it: the merge kernels only read the partials of the blocks that exist.
 // The spans of a level are consecutive nodes, so the rows are written 16 bytes per lane.
-__device__ __forceinline__ void span_block_gone(const SpanArgs& a, int bh, int blk, int t0, int nblk, int nanc,
-                                                int64_t base, bool forward, int lane) {
+__device__ __forceinline__ void span_block_gone(const SpanArgs& a, int bh, int t0, int64_t base, bool forward, int lane) {
     const int top = min(kSpanInLevels, a.L);
     for (int level = 1; level <= top; ++level) {
         const int node0 = span_level_offset(a.n, level) + (t0 >> level), cnt = kSpanTok >> level;
         if (forward) {
+            if (a.leave_unkept) continue;
             for (int i = lane; i < cnt * 8; i += 64)     // 64 bf16 per row
                 *reinterpret_cast<uint4*>(a.out + base + (int64_t)(node0 + (i >> 3)) * a.sn + (i & 7) * 8) = make_uint4(0u, 0u, 0u, 0u);
             if (lane < cnt) a.lse[(int64_t)bh * a.N + node0 + lane] = 0.f;
         } else {
-            for (int i = lane; i < cnt * 16; i += 64)    // 64 floats per row
-                *reinterpret_cast<float4*>(a.dQ + base + (int64_t)(node0 + (i >> 4)) * a.sn + (i & 15) * 4) = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (!a.leave_unkept)
+                for (int i = lane; i < cnt * 16; i += 64)    // 64 floats per row
+                    *reinterpret_cast<float4*>(a.dQ + base + (int64_t)(node0 + (i >> 4)) * a.sn + (i & 15) * 4) = make_float4(0.f, 0.f, 0.f, 0.f);
             if (lane < cnt) a.stat[(int64_t)bh * a.N + node0 + lane] = make_float2(kLseGone, 0.f);
         }
-    }
-    const int stride = forward ? kPartStride : kQPartStride;   // 66: sums, max, weight; 132: A, Bv, delta, padding
-    for (int slot = 0; slot < nanc; ++slot) {
-        float* dst = a.part + (((int64_t)bh * nanc + slot) * nblk + blk) * stride;
-        for (int i = lane; i < stride; i += 64) dst[i] = forward && i == 64 ? kNegBig : 0.f;
     }
 }
 
@@ -119,7 +117,7 @@ __global__ void __launch_bounds__(kTileThreads) fwd_span_tile_kernel(const SpanA
 
     // the block's K rows as A operands (token j of chunk c, features 16g..16g+15); V rows into LDS
     if (t0 >= len) {   // wave-uniform: a block past the end of a shorter sequence
-        span_block_gone(a, bh, blk, t0, nblk, nanc, base, true, lane);
+        span_block_gone(a, bh, t0, base, true, lane);
         return;
     }
     // the query rows of all three groups are asked for together with the block's K and V: one round trip
@@ -254,7 +252,7 @@ constexpr int kSpanSmallLevels = 4;                                  // levels 6
 constexpr int kSpanSmallMax = 1 << kSpanSmallLevels;                 // 16 partials
 constexpr int kSpanBigThreads = 1024;
 struct SpanRow {
-    int bh, v, cnt;
+    int bh, v, cnt;   // cnt: partials of the row that exist -- its blocks that begin before the end of the sequence
     const float* src;
 };
 // rows [first, first + rows) of every (batch, head); stride = floats per partial
@@ -265,8 +263,10 @@ __device__ __forceinline__ bool span_merge_row(const SpanArgs& a, int item, int 
     int level, mi;
     span_node_level(a.n, a.L, r.v, level, mi);
     const int nblk = a.n / kSpanTok, nanc = a.L - kSpanInLevels;
-    r.cnt = 1 << (level - kSpanInLevels);
-    r.src = a.part + (((int64_t)r.bh * nanc + (level - kSpanInLevels - 1)) * nblk + (int64_t)mi * r.cnt) * stride;
+    const int all = 1 << (level - kSpanInLevels);
+    const int live_blocks = (seq_length(a.seq_len, r.bh / a.H, a.n) + kSpanTok - 1) / kSpanTok;
+    r.cnt = min(all, max(live_blocks - mi * all, 0));
+    r.src = a.part + (((int64_t)r.bh * nanc + (level - kSpanInLevels - 1)) * nblk + (int64_t)mi * all) * stride;
     return true;
 }
 
@@ -281,13 +281,14 @@ __device__ __forceinline__ void fwd_span_merge_small(const SpanArgs& a, int item
     const int lane = threadIdx.x & 63;
     SpanRow r;
     if (!span_merge_row(a, item, first, rows, kPartStride, r)) return;
+    if (r.cnt == 0 && a.leave_unkept) return;   // the sequence does not keep the node
     float o[kSpanSmallMax], m[kSpanSmallMax], l[kSpanSmallMax];
 #pragma unroll
     for (int b = 0; b < kSpanSmallMax; ++b) {
-        const float* pb = r.src + (int64_t)min(b, r.cnt - 1) * kPartStride;
-        o[b] = pb[lane];
+        const float* pb = r.src + (int64_t)max(min(b, r.cnt - 1), 0) * kPartStride;
+        o[b] = b < r.cnt ? pb[lane] : 0.f;
         m[b] = b < r.cnt ? pb[64] : kNegBig;
-        l[b] = pb[65];
+        l[b] = b < r.cnt ? pb[65] : 0.f;
     }
     float mx = kNegBig;
 #pragma unroll
@@ -317,6 +318,7 @@ __global__ void __launch_bounds__(kSpanBigThreads) fwd_span_merge_kernel(const S
     }
     SpanRow r;
     if (!span_merge_row(a, blockIdx.x - small_blocks, first_big, rows_big, kPartStride, r)) return;   // uniform for the workgroup
+    if (r.cnt == 0 && a.leave_unkept) return;
     const int t = threadIdx.x, fq = t & 15, pl = t >> 4;
     float mx = kNegBig;
     for (int b = t; b < r.cnt; b += kSpanBigThreads) mx = fmaxf(mx, r.src[(int64_t)b * kPartStride + 64]);
@@ -378,7 +380,7 @@ __global__ void __launch_bounds__(kTileThreads, 3) bwd_q_span_tile_kernel(const 
     const int len = seq_length(a.seq_len, bh / a.H, a.n);
 
     if (t0 >= len) {   // wave-uniform: a block past the end of a shorter sequence
-        span_block_gone(a, bh, blk, t0, nblk, nanc, base, false, lane);
+        span_block_gone(a, bh, t0, base, false, lane);
         return;
     }
     // the Q and dO rows and the lse of all three groups are asked for together with the block's K and V:
@@ -519,10 +521,14 @@ __device__ __forceinline__ void bwd_q_span_merge_small(const SpanArgs& a, int it
     const int lane = threadIdx.x & 63;
     SpanRow r;
     if (!span_merge_row(a, item, first, rows, kQPartStride, r)) return;
+    if (r.cnt == 0 && a.leave_unkept) {   // the sequence does not keep the node: only the switch for the key side
+        if (lane == 0) a.stat[(int64_t)r.bh * a.N + r.v] = make_float2(kLseGone, 0.f);
+        return;
+    }
     float xa[kSpanSmallMax], xb[kSpanSmallMax], xd[kSpanSmallMax];
 #pragma unroll
     for (int b = 0; b < kSpanSmallMax; ++b) {
-        const float* pb = r.src + (int64_t)min(b, r.cnt - 1) * kQPartStride;
+        const float* pb = r.src + (int64_t)max(min(b, r.cnt - 1), 0) * kQPartStride;
         xa[b] = pb[lane];
         xb[b] = pb[kD + lane];
         xd[b] = pb[2 * kD];
@@ -550,6 +556,10 @@ __global__ void __launch_bounds__(kSpanBigThreads) bwd_q_span_merge_kernel(const
     }
     SpanRow r;
     if (!span_merge_row(a, blockIdx.x - small_blocks, first_big, rows_big, kQPartStride, r)) return;
+    if (r.cnt == 0 && a.leave_unkept) {
+        if (threadIdx.x == 0) a.stat[(int64_t)r.bh * a.N + r.v] = make_float2(kLseGone, 0.f);
+        return;
+    }
     const int t = threadIdx.x, fq = t & 15, pl = t >> 4;
     float4 sa = make_float4(0.f, 0.f, 0.f, 0.f), sb = sa;
     float dl = 0.f;

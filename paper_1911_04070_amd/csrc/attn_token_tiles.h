@@ -52,6 +52,7 @@ struct TileArgs {
     float* drel_part;   // DENSE variant: the workgroups' copies of d_rel, [workgroup][cid_pad][64]
     // sequences shorter than n
     const int32_t *seq_len, *id_to_cid;
+    int32_t leave_unkept;   // rows of nodes a shorter sequence does not keep: left unwritten instead of zero-filled
     int32_t n, k, W, ctx_levels, causal;
     // dropout on the attention weights (DROP variants of the kernels)
     uint32_t drop_thr, drop_seed;
@@ -225,6 +226,7 @@ __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArg
     const bool compact = a.seq_len && nbatch <= kMaxLenBatch;
     int live_total = 0;
     auto zero_rows = [&](int bh, int tile) {   // out and lse of a tile past the end of its sequence
+        if (a.leave_unkept) return;
         const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
         bf16_t* orow = a.out + base + (int64_t)(tile * 16 + r8) * a.sn + piece * 8;
         *reinterpret_cast<uint4*>(orow) = make_uint4(0u, 0u, 0u, 0u);
@@ -234,7 +236,7 @@ __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArg
     if (compact) {
         live_tiles_prefix(pref_s, a.seq_len, nbatch, a.n, a.num_tiles);
         live_total = a.H * pref_s[nbatch];
-        const int dead_total = a.BH * a.num_tiles - live_total;
+        const int dead_total = a.leave_unkept ? 0 : a.BH * a.num_tiles - live_total;
         for (TileWalk wd((dead_total + kTileWaves - 1) / kTileWaves); wd.t < wd.t_end; wd.t += wd.step) {
             const int idx = wd.t * kTileWaves + wave;
             if (idx < dead_total) {
@@ -546,10 +548,12 @@ __global__ void __launch_bounds__(kTileThreads, DENSE ? 1 : 2) bwd_q_tile_kernel
     auto zero_rows = [&](int bh, int tile) {   // dQ of a tile past the end of its sequence; `stat` switches its rows off on the key side
         const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
         float* qrow = a.dQ + base + (int64_t)(tile * 16 + r8) * a.sn + piece * 8;
+        if (!a.leave_unkept) {
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            *reinterpret_cast<float4*>(qrow + (int64_t)8 * h * a.sn) = make_float4(0.f, 0.f, 0.f, 0.f);
-            *reinterpret_cast<float4*>(qrow + (int64_t)8 * h * a.sn + 4) = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int h = 0; h < 2; ++h) {
+                *reinterpret_cast<float4*>(qrow + (int64_t)8 * h * a.sn) = make_float4(0.f, 0.f, 0.f, 0.f);
+                *reinterpret_cast<float4*>(qrow + (int64_t)8 * h * a.sn + 4) = make_float4(0.f, 0.f, 0.f, 0.f);
+            }
         }
         if (lane < 16) a.stat[(int64_t)bh * a.N + tile * 16 + lane] = make_float2(kLseGone, 0.f);
     };

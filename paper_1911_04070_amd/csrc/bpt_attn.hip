@@ -149,6 +149,7 @@ void fill_common(AttnArgs& a, const bpt_graph* g, const bpt_shape_t* s) {
     a.slab_bytes = (uint32_t)(((int64_t)(g->num_nodes - 1) * s->stride_n + kD) * es);
     a.idx_bytes = (uint32_t)(g->num_edges * 4);
     a.seq_len = s->seq_len;
+    a.leave_unkept = s->seq_len && s->leave_unkept ? 1 : 0;
     a.lg = g->num_levels - 1;
     const double p = s->dropout_p > 0.f ? (double)s->dropout_p : 0.0;
     a.drop_thr = p > 0.0 ? (uint32_t)std::min(std::floor(p * 4294967296.0), 4294967295.0) : 0u;
@@ -260,6 +261,7 @@ void fill_tile_args(TileArgs& t, const bpt_graph* g, const AttnArgs& a, const Ti
     t.row_bytes = a.row_bytes;
     t.slab_bytes = a.slab_bytes;
     t.seq_len = a.seq_len;
+    t.leave_unkept = a.leave_unkept;
     t.id_to_cid = g->tiles.id_to_cid;
     t.n = g->n;
     t.k = g->k;
@@ -307,6 +309,7 @@ void fill_span_args(SpanArgs& t, const bpt_graph* g, const AttnArgs& a) {
     t.zero = g->k + 1;
     t.scale = a.scale;
     t.seq_len = a.seq_len;
+    t.leave_unkept = a.leave_unkept;
     t.drop_thr = a.drop_thr;
     t.drop_seed = a.drop_seed;
     t.drop_inv_keep = a.drop_inv_keep;
@@ -665,6 +668,7 @@ int run_bwd_kv_tiles(const bpt_graph* g, const BwdPlan& p, const AttnArgs& a, co
     t.zero = g->k + 1;
     t.num_chunks = kt.num_chunks;
     t.seq_len = a.seq_len;
+    t.leave_unkept = a.leave_unkept;
     t.n = g->n;
     t.drop_thr = a.drop_thr;
     t.drop_seed = a.drop_seed;
@@ -691,7 +695,7 @@ int run_bwd_kv_tiles(const bpt_graph* g, const BwdPlan& p, const AttnArgs& a, co
     }
     if (rc) return rc;
     // threads of the zero pass of kv_tile_merge_kernel: one per node it has to look at, in wavefronts of 64 nodes
-    const int zero_row0 = a.seq_len ? 0 : (kt.first_uncovered & ~63);
+    const int zero_row0 = a.seq_len && !a.leave_unkept ? 0 : (kt.first_uncovered & ~63);
     const int64_t zero_elems = (int64_t)a.BH * ((a.N - zero_row0 + 63) / 64) * 64;
     const int64_t blocks = (int64_t)a.BH * kt.num_multi + (zero_elems + 255) / 256;
     if (blocks > 0) {

@@ -285,6 +285,51 @@ def test_lengths_with_node_major_memory_and_many_ids():
     g.destroy()
 
 
+@pytest.mark.parametrize("dtype,n,k,causal,H,lengths", [
+    ("bf16", 512, 4, False, 2, [512, 300, 33, 1, 0]), ("bf16", 4096, 8, True, 1, [3000, 4096, 129]),
+    ("bf16", 2048, 16, False, 1, [2047, 1025]), ("bf16", 8192, 8, True, 2, [1332, 7532]), ("f32", 256, 3, True, 1, [100, 256, 2]),
+])
+def test_rows_of_unkept_nodes_left_unwritten(dtype, n, k, causal, H, lengths):
+    # bpt_shape_t.leave_unkept: the rows of kept nodes are those of the zero-filling calls bit for bit, and so is
+    # d_rel; no NaN or Inf appears anywhere (the buffers start from a finite pattern).  With the matrix-core
+    # kernels (bf16) the rows of whole tiles and blocks past the end of a sequence still hold that pattern.
+    say("leave unkept", dtype, n, k, causal, H, lengths)
+    w = Workload("unkept", 28, n, k, causal, len(lengths), H, 64, dtype, True)
+    x = make_inputs(w)
+    g = bpt.bpt_build_graph(n, k, causal)
+    Q, K, V, dO, R = (to_dev(x[k_], dtype) for k_ in ("Q", "K", "V", "dO", "Rel"))
+    lens_d = torch.tensor(list(lengths), dtype=torch.int32, device="cuda")
+    out0, lse0 = bpt.bpt_attn_fwd(g, Q, K, V, R, scale=w.scale, seq_len=lens_d)
+    grads0 = bpt.bpt_attn_bwd(g, Q, K, V, R, lse0, dO, scale=w.scale, seq_len=lens_d)
+    mark = 7.0
+    out1 = torch.full_like(Q, mark)
+    lse1 = torch.full(Q.shape[:3], mark, dtype=torch.float32, device="cuda")
+    grads1 = tuple(torch.full(Q.shape, mark, dtype=torch.float32, device="cuda") for _ in range(3)) + (
+        torch.full(R.shape, mark, dtype=torch.float32, device="cuda"),)
+    bpt.bpt_attn_fwd(g, Q, K, V, R, scale=w.scale, seq_len=lens_d, out=out1, lse=lse1, leave_unkept=True)
+    lse_in = torch.where(lse1 == mark, torch.zeros_like(lse1), lse1)   # the backward reads lse of kept rows only
+    bpt.bpt_attn_bwd(g, Q, K, V, R, lse_in, dO, scale=w.scale, seq_len=lens_d, grads=grads1, leave_unkept=True)
+    torch.cuda.synchronize()
+    assert torch.equal(grads0[3], grads1[3])          # d_rel does not depend on the option
+    untouched = 0
+    for b, length in enumerate(lengths):
+        deg = np.diff(oracle.build_graph_len(n, max(int(length), 1), k, causal).row_ptr)
+        kept = torch.from_numpy(np.flatnonzero(deg > 0) if length >= 1 else np.zeros(0, dtype=np.int64)).cuda()
+        gone = np.flatnonzero(deg == 0) if length >= 1 else np.arange(2 * n - 1)
+        for name, a0, a1 in zip(("out", "lse", "dQ", "dK", "dV"), (out0, lse0) + tuple(grads0[:3]), (out1, lse1) + tuple(grads1[:3])):
+            assert torch.equal(a0[b][:, kept], a1[b][:, kept]), (name, b)
+            assert bool(torch.isfinite(a1[b].float()).all()), (name, b)
+        # nodes of whole token tiles / span blocks past the end: nothing was written there
+        far = torch.from_numpy(gone[(gone >= ((length + 31) // 32) * 32) & (gone < n)]).cuda()
+        if dtype == "bf16" and n >= 64 and len(far):
+            untouched += int(far.numel())
+            for name, a1 in zip(("out", "dQ", "dK", "dV"), (out1,) + tuple(grads1[:3])):
+                assert bool((a1[b][:, far].float() == mark).all()), (name, b)
+    if dtype == "bf16" and min(lengths) + 64 <= n:
+        assert untouched > 0
+    g.destroy()
+
+
 def test_lengths_equal_to_n_change_nothing():
     w = Workload("full_lengths", 22, 1024, 4, False, 2, 2, 64, "bf16", True)
     x = make_inputs(w)
