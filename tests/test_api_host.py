@@ -81,9 +81,10 @@ def test_null_graph_is_an_error_everywhere():
 
 def test_shape_struct_layout_matches_the_header():
     # int32 B,H,D,dtype; int64 stride_b,stride_h,stride_n; float scale (+ padding); pointer seq_len;
-    # float dropout_p; uint32 dropout_seed
-    assert ctypes.sizeof(bpt.BptShape) == 64
+    # float dropout_p; uint32 dropout_seed; int32 leave_unkept (+ padding)
+    assert ctypes.sizeof(bpt.BptShape) == 72
     assert bpt.BptShape.dropout_p.offset == 56 and bpt.BptShape.dropout_seed.offset == 60
+    assert bpt.BptShape.leave_unkept.offset == 64
     assert bpt.BptShape.stride_b.offset == 16 and bpt.BptShape.scale.offset == 40
     assert bpt.BptShape.seq_len.offset == 48
 
