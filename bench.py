@@ -468,7 +468,7 @@ def main():
         import oracle
         og = oracle.build_graph(w.n, w.k, w.causal)
         passes, dt, used = 0, 0.0, 1
-        while passes < 1 or (dt < 5.0 and passes < 50):      # a few seconds of wall time on all cores
+        while passes < 1 or (dt < 10.0 and passes < 50):     # about ten seconds of wall time on all cores
             t0 = time.perf_counter()
             if lengths is not None:
                 oracle.attn_fwd_lengths(w.n, w.k, w.causal, lengths, x["Q"], x["K"], x["V"], x["Rel"], w.scale)

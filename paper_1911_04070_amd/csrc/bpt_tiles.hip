@@ -17,7 +17,7 @@ constexpr int kScanBlock = kTB * kScanItems;   // elements per block of the scan
 constexpr int kMaxLevels = 24;                 // n <= 2^22
 constexpr int kMaxSortedTasks = 1 << 16;       // key-tile tasks are put in stretch order up to this many (the ordering is quadratic)
 constexpr int kMaxBuckets = 2 * kMaxLevels;
-constexpr int kChainChunks = 8;                // key tiles of at most this many chunks are chained
+constexpr int kChainChunks = 16;               // key tiles of at most this many chunks are chained
 
 __host__ __device__ inline int level_off(int n, int level) { return 2 * n - ((2 * n) >> level); }
 

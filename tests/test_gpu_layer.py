@@ -88,11 +88,17 @@ def test_layer_forward(n, k, causal, B, heads, d_ff, zero_spans, lengths):
 #  * `decisive`: b1 = +6 or -6 by column, which puts every pre-activation (unit variance) six deviations
 #    from zero; both sides then take the same gate, half of the units on, and what remains is rounding:
 #    measured 0.1..0.6 % of the largest entry, bound 1.5 %;
-#  * ordinary biases: the same comparison with the bound 15 %, which still separates a correct backward
-#    from a wrong operand, transpose or sign (those give errors of the order of the tensor itself).
+#  * ordinary biases: the gradients that do not pass through the gate's derivative (dW2, db2, dg2, dbeta2: they
+#    are formed from dY, the stored sums and the hidden activations themselves, which are continuous in the
+#    pre-activation) keep the bound of the decisive cases, 1.5 % (measured 0.2..0.4 %); the others get 15 %
+#    (measured 2..10 %, the sqrt(f) above), which still separates a correct backward from a wrong operand,
+#    transpose or sign (those give errors of the order of the tensor itself).  A bound that holds for every
+#    choice of the ambiguous gates (the sum of the absolute contributions of all units within the forward's
+#    error of zero) exceeds the tensors themselves for sums over a thousand rows, so it would check nothing.
 from oracle.layer import kept_rows, layer_backward   # noqa: E402
 
 BWD_TOL_DECISIVE, BWD_TOL_ORDINARY = 1.5e-2, 15e-2
+GATE_FREE = ("dW2", "db2", "dg2", "dbeta2")   # no factor of the ReLU's derivative in them
 GRADS = ("dWq", "dWk", "dWv", "dWo", "dW1", "db1", "dW2", "db2", "dg1", "dbeta1", "dg2", "dbeta2")
 
 
@@ -128,8 +134,8 @@ def test_layer_backward(n, k, causal, B, heads, d_ff, lengths, decisive):
         top = float(np.abs(ref[name]).max())
         worst[name] = float(np.abs(a - ref[name]).max()) / max(top, 1e-30)
     print("   relative max-abs errors", {k_: float("%.2g" % v) for k_, v in worst.items()}, flush=True)
-    tol = BWD_TOL_DECISIVE if decisive else BWD_TOL_ORDINARY
     for name, v in worst.items():
+        tol = BWD_TOL_DECISIVE if decisive or name in GATE_FREE else BWD_TOL_ORDINARY
         assert v <= tol, (name, v)
     if lengths:   # rows of nodes a sequence does not keep get exactly no gradient
         gone = torch.from_numpy(~kept_rows(n, lengths)).cuda()
