@@ -29,11 +29,12 @@ KERNEL_SOURCES = os.path.join(ROOT, "paper_1911_04070_amd", "csrc")
 
 
 def kernel_source_hash():
-    """sha256 over the kernel sources: the counter figures in profiles/ belong to one build of the kernels."""
+    """sha256 over the sources of the graph and attention kernels (not the layer around them, whose kernels are not
+    in that file): the counter figures in profiles/ belong to one build of the kernels."""
     import hashlib
     h = hashlib.sha256()
     for name in sorted(os.listdir(KERNEL_SOURCES)):
-        if name.endswith((".h", ".hip")):
+        if name.endswith((".h", ".hip")) and name != "bpt_layer.hip":
             with open(os.path.join(KERNEL_SOURCES, name), "rb") as f:
                 h.update(name.encode() + b"\0" + f.read())
     return h.hexdigest()[:16]
@@ -374,7 +375,7 @@ def main():
     alg_bytes = {
         "fwd_tile_kernel": gather * tok_inst, "bwd_q_tile_kernel": gather * tok_inst,
         "fwd_span_tile_kernel": gather * span_inst, "bwd_q_span_tile_kernel": gather * span_inst,
-        "bwd_kv_tile_kernel": gather * edge_inst, "bwd_kv_kernel": gather * edge_inst,
+        "bwd_kv_tile_kernel": gather * edge_inst, "bwd_kv_chain_kernel": gather * edge_inst, "bwd_kv_kernel": gather * edge_inst,
     }
     # the gather kernels take whatever rows the tile kernels of this launch did not
     alg_bytes["fwd_kernel"] = gather * (edge_inst - (tok_inst if "fwd_tile_kernel" in kernel_ms else 0) - (
@@ -397,7 +398,7 @@ def main():
         # Q and dout rows of every query node with (lse, delta), K and V rows of the keys; dK and dV rows (fp32) out
         "bwd_kv_tile_kernel": bh * (n_all * 2 * row + n_all * 8 + keyed * 2 * row + keyed * 2 * frow),
     }
-    compulsory_kernel["bwd_kv_kernel"] = compulsory_kernel["bwd_kv_tile_kernel"]
+    compulsory_kernel["bwd_kv_kernel"] = compulsory_kernel["bwd_kv_chain_kernel"] = compulsory_kernel["bwd_kv_tile_kernel"]
     rows_fwd = n_all - (n_tok if "fwd_tile_kernel" in kernel_ms else 0) - (n_span if "fwd_span_tile_kernel" in kernel_ms else 0)
     rows_bq = n_all - (n_tok if "bwd_q_tile_kernel" in kernel_ms else 0) - (n_span if "bwd_q_span_tile_kernel" in kernel_ms else 0)
     keys_of = lambda rows: keyed if rows > n_span else n_tok   # all rows: every keyed node; span rows only: the tokens
@@ -425,7 +426,7 @@ def main():
         step_traffic = int(sum((r + wr) * launches for r, wr, launches in per_kernel.values()))
     # matrix-core work of the dominant kernel if its tiles were full: 2 * 64 flops per edge-instance and product
     products = {"fwd_tile_kernel": 3, "fwd_span_tile_kernel": 2, "bwd_q_tile_kernel": 6, "bwd_q_span_tile_kernel": 4,
-                "bwd_kv_tile_kernel": 5}.get(dominant)
+                "bwd_kv_tile_kernel": 5, "bwd_kv_chain_kernel": 5}.get(dominant)
     roofline = {
         "bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
         "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
