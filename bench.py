@@ -86,6 +86,9 @@ def parse():
     ap.add_argument("--zero-unkept", action="store_true",
                     help="workloads with sequences of different lengths: zero-fill the rows of nodes a sequence does not "
                          "keep (the default leaves them unwritten, bpt_shape_t.leave_unkept)")
+    ap.add_argument("--packed", action="store_true",
+                    help="workloads with sequences of different lengths: one graph for the whole batch with rows only for "
+                         "the nodes that exist (bpt_build_batch_graph) instead of the padded trees")
     ap.add_argument("--regions", type=int, default=5,
                     help="the timed steps are run as this many back-to-back regions (each synchronised on both sides); "
                          "ms_per_step is the median region, the spread is reported beside it")
@@ -150,6 +153,73 @@ def bench_stack(args, w, bpt, torch, np):
                    "output": "tokens" if tokens_out else "root"},
         "dense_TFLOPs": round(flops / (ms * 1e-3) / 1e12, 1),
         "workspace_GB": round((fws + bws) / 1e9, 2),
+    }), flush=True)
+
+
+def bench_packed(args, w, bpt, torch, np):
+    """Attention forward + backward of a workload whose sequences have different lengths, on ONE graph for the batch
+    with rows only for the nodes that exist (bpt_build_batch_graph): tensors [1, H, rows, 64], no padding anywhere."""
+    from paper_1911_04070_amd.workloads import make_lengths
+    lengths = make_lengths(w)
+    tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    g = bpt.bpt_build_batch_graph(w.n, w.k, w.causal, lengths)
+    torch.cuda.synchronize()
+    build_ms = (time.perf_counter() - t0) * 1e3
+    gen = torch.Generator(device="cuda").manual_seed(1911 + w.index)
+    rnd = lambda *shape, s=1.0: (s * torch.randn(*shape, device="cuda", generator=gen)).to(tdt)
+    Q, K, V, dO = (rnd(1, w.H, g.num_nodes, w.D) for _ in range(4))
+    R = rnd(g.num_levels, g.rel_width, w.D, s=0.02)
+    out = torch.empty_like(Q)
+    lse = torch.empty(Q.shape[:3], dtype=torch.float32, device="cuda")
+    grads = tuple(torch.empty(Q.shape, dtype=torch.float32, device="cuda") for _ in range(3)) + (
+        torch.empty(R.shape, dtype=torch.float32, device="cuda"),)
+    fws, bws = bpt.workspace_bytes(g, Q, w.scale)
+    ws_f = torch.empty(max(fws, 256), dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(max(bws, 256), dtype=torch.uint8, device="cuda")
+
+    def step():
+        bpt.bpt_attn_fwd(g, Q, K, V, R, scale=w.scale, out=out, lse=lse, workspace=ws_f)
+        if w.backward:
+            bpt.bpt_attn_bwd(g, Q, K, V, R, lse, dO, scale=w.scale, grads=grads, workspace=ws_b)
+
+    for _ in range(args.warmup):
+        step()
+    regions = max(1, min(args.regions, args.steps))
+    sizes = [args.steps // regions + (1 if r < args.steps % regions else 0) for r in range(regions)]
+    region_ms = []
+    torch.cuda.synchronize()
+    for count in sizes:
+        t0 = time.perf_counter()
+        for _ in range(count):
+            step()
+        torch.cuda.synchronize()
+        region_ms.append((time.perf_counter() - t0) * 1e3 / count)
+    ms = float(np.median(region_ms))
+    bpt.bpt_profile_enable(True)
+    for _ in range(10):
+        step()
+    torch.cuda.synchronize()
+    prof = bpt.bpt_profile_report()
+    bpt.bpt_profile_enable(False)
+    edge_inst = w.H * g.num_edges
+    es = 2 if w.dtype == "bf16" else 4
+    padded_rows = w.B * (2 * w.n - 1)
+    print(json.dumps({
+        "metric": "BPT graph-attention fwd+bwd edges/sec" if w.backward else "BPT graph-attention fwd edges/sec",
+        "value": round(edge_inst / (ms * 1e-3), 1), "unit": "edges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 4), "ms_per_step_min": round(min(region_ms), 4), "ms_per_step_max": round(max(region_ms), 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name + "+packed", "n": w.n, "k": w.k, "causal": w.causal, "batch": w.B, "heads": w.H,
+                   "layout": "one graph for the batch, rows of kept nodes only", "rows": g.num_nodes,
+                   "padded_rows": padded_rows, "tokens": g.n_tokens, "edges_per_head": g.num_edges,
+                   "lengths": [int(v) for v in lengths]},
+        "graph_build_ms": round(build_ms, 3),
+        "tensor_MB": {"packed_per_tensor": round(w.H * g.num_nodes * w.D * es / 1e6, 2),
+                      "padded_per_tensor": round(w.H * padded_rows * w.D * es / 1e6, 2),
+                      "workspace": round((fws + bws) / 1e6, 2)},
+        "kernel_ms": {name: round(total / calls, 5) for name, (calls, total) in prof.items()},
     }), flush=True)
 
 
@@ -258,6 +328,10 @@ def main():
     torch.cuda.set_device(0)
     if args.layer:
         return (bench_stack if args.layers > 1 else bench_layer)(args, w, bpt, torch, np)
+    if args.packed:
+        if not w.length_mix:
+            sys.exit("--packed is for the workloads with sequences of different lengths (lm_lengths, cls_lengths)")
+        return bench_packed(args, w, bpt, torch, np)
     tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
     bytes_scale = 1.0 if w.dtype == "bf16" else 2.0
 

@@ -104,6 +104,35 @@ typedef struct {
  * the library until bpt_graph_destroy.  Synchronises `stream`. */
 int bpt_build_graph(int32_t n, int32_t k, int32_t causal, void* stream, bpt_graph_t** out);
 
+/* Sec. 4.1 (batches of sequences of different lengths; the appendix on implementation
+ * details: the graphs of a batch are joined into one).  Builds, on the current device, ONE
+ * graph for a batch of `batch` sequences, sequence b holding lengths[b] tokens (host array,
+ * 0 <= lengths[b] <= n, at least one token in all; 1 <= batch <= 65536): the disjoint union
+ * of the graphs that "Sequences shorter than n" above defines for each length on the tree
+ * over n (n, k, causal as for bpt_build_graph).  Only kept nodes get a row, so tensors,
+ * workspaces and work follow the tokens that exist instead of batch * (2n-1).
+ * Row numbering ("packed", see bpt_graph_layout): level-major over the batch -- the tokens of
+ * sequence 0, of sequence 1, ..., then the level-1 nodes of sequence 0, of sequence 1, ... up
+ * to the root level; node (level l, index m) of sequence b is row first_row[l][b] + m and
+ * level l of that sequence has ceil(lengths[b] / 2^l) rows.  col / t_src hold packed rows;
+ * rel ids and the canonical order within a row are those of the single-sequence graph, and
+ * the relative-position table is shared by all sequences (Sec. 3.4).
+ * The attention calls (and bpt_layer_fwd / bpt_layer_bwd) take such a graph like any other,
+ * with N = its row count, B = 1 (or B independent batches of the same length mix) and
+ * seq_len = NULL (BPT_ERR_INVALID_ARG otherwise); they run the library's gather kernels on
+ * it (the dense-tile kernels are built for the tree of one sequence).  Dropout on the
+ * attention weights and the bpt_stack_* calls are refused on it (BPT_ERR_UNSUPPORTED).
+ * More than 2^23 rows: BPT_ERR_UNSUPPORTED.  Synchronises `stream`. */
+int bpt_build_batch_graph(int32_t n, int32_t k, int32_t causal, const int32_t* lengths, int32_t batch,
+                          void* stream, bpt_graph_t** out);
+
+/* Row layout of a graph: *batch = sequences in it (1 for bpt_build_graph), *n_tokens = token
+ * rows (they come first), and, into host arrays of num_levels * batch entries indexed
+ * [level * batch + b], first_row = row of node (level, 0) of sequence b and row_count = nodes
+ * of that level the sequence keeps.  NULL skips an output. */
+int bpt_graph_layout(const bpt_graph_t* g, int32_t* batch, int32_t* n_tokens, int32_t* first_row,
+                     int32_t* row_count);
+
 /* Any output pointer may be NULL.  num_levels = log2(n)+1, rel_width = W,
  * ctx_levels = number of levels on which some token has contextual nodes. */
 int bpt_graph_info(const bpt_graph_t* g, int32_t* n, int32_t* k, int32_t* causal,

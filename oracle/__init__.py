@@ -224,3 +224,58 @@ def attn_bwd_lengths(n, k, causal, lengths, Q, K, V, Rel, dO, scale: float, thre
         dQ[b:b + 1], dK[b:b + 1], dV[b:b + 1] = q, kk, v
         dRel = r if dRel is None else dRel + r
     return dQ, dK, dV, dRel
+
+
+def batch_layout(n: int, lengths):
+    """Rows of a batch of sequences joined into one graph, only kept nodes getting a row: level-major over the
+    batch (all tokens first, sequence by sequence, then the level-1 nodes, ...).  Level l of a sequence of
+    len tokens keeps ceil(len / 2^l) nodes.  Returns (first_row[l][b], row_count[l][b], rows)."""
+    L = num_levels(n)
+    first = np.zeros((L, len(lengths)), dtype=np.int64)
+    count = np.zeros((L, len(lengths)), dtype=np.int64)
+    row = 0
+    for l in range(L):
+        for b, length in enumerate(lengths):
+            count[l, b] = -(-int(length) // (1 << l))
+            first[l, b] = row
+            row += int(count[l, b])
+    return first, count, row
+
+
+def batch_rows(n: int, lengths):
+    """(row_of[b][node of the tree over n] or -1, sequence of every row, tree node of every row) of batch_layout."""
+    first, count, rows = batch_layout(n, lengths)
+    row_of = -np.ones((len(lengths), 2 * n - 1), dtype=np.int64)
+    b_of = np.zeros(rows, dtype=np.int64)
+    node_of = np.zeros(rows, dtype=np.int64)
+    for l in range(first.shape[0]):
+        off = level_offset(n, l)
+        for b in range(len(lengths)):
+            c, r0 = int(count[l, b]), int(first[l, b])
+            row_of[b, off:off + c] = r0 + np.arange(c)
+            b_of[r0:r0 + c] = b
+            node_of[r0:r0 + c] = off + np.arange(c)
+    return row_of, b_of, node_of
+
+
+def build_batch_graph(n: int, k: int, causal: bool, lengths) -> Graph:
+    """The graphs of a batch of sequences (build_graph_len of every length, Sec. 3.2 on the kept nodes) joined
+    into one graph over the rows of batch_layout: the disjoint union, every row keeping its edges in their
+    order with the key nodes renumbered.  (The paper batches the graphs of its sentences in the same way,
+    Sec. 4.1 and the appendix on implementation details.)  Graph.num_nodes is the row count."""
+    row_of, b_of, node_of = batch_rows(n, lengths)
+    rows = len(b_of)
+    per = [build_graph_len(n, int(length), k, causal) if length >= 1 else None for length in lengths]
+    row_ptr = np.zeros(rows + 1, dtype=np.int32)
+    cols, rels = [np.zeros(0, dtype=np.int32)], [np.zeros(0, dtype=np.int32)]
+    for r in range(rows):
+        g, u = per[b_of[r]], node_of[r]
+        e0, e1 = int(g.row_ptr[u]), int(g.row_ptr[u + 1])
+        c = row_of[b_of[r], g.col[e0:e1]]
+        if e1 <= e0 or (c < 0).any():
+            raise RuntimeError("a kept node without edges, or an edge to a node that is not kept")
+        cols.append(c.astype(np.int32))
+        rels.append(g.rel[e0:e1].astype(np.int32))
+        row_ptr[r + 1] = row_ptr[r] + (e1 - e0)
+    return Graph(n, k, bool(causal), rows, num_levels(n), int(_load().bpto_rel_width(k)), row_ptr,
+                 np.concatenate(cols), np.concatenate(rels))

@@ -21,7 +21,7 @@ BPT_OK, BPT_ERR_INVALID_ARG, BPT_ERR_UNSUPPORTED, BPT_ERR_ALLOC, BPT_ERR_LAUNCH,
 BPT_STATIC_SCRATCH_BYTES = 32 << 20
 
 EXPORTS = [
-    "bpt_build_graph", "bpt_graph_info", "bpt_graph_csr", "bpt_graph_transposed", "bpt_graph_to_host",
+    "bpt_build_graph", "bpt_build_batch_graph", "bpt_graph_layout", "bpt_graph_info", "bpt_graph_csr", "bpt_graph_transposed", "bpt_graph_to_host",
     "bpt_graph_transposed_to_host", "bpt_graph_destroy", "bpt_attn_fwd_workspace", "bpt_attn_bwd_workspace",
     "bpt_attn_fwd", "bpt_attn_fwd_static", "bpt_attn_bwd", "bpt_attn_bwd_query_side", "bpt_attn_bwd_key_side", "bpt_profile_enable",
     "bpt_profile_report", "bpt_calibrate_gather", "bpt_layer_fwd_workspace", "bpt_layer_fwd", "bpt_layer_bwd_workspace", "bpt_layer_bwd",
@@ -72,6 +72,10 @@ def load_library() -> ctypes.CDLL:
     P = ctypes.POINTER
     L.bpt_build_graph.restype = ctypes.c_int
     L.bpt_build_graph.argtypes = [i32, i32, i32, vp, P(vp)]
+    L.bpt_build_batch_graph.restype = ctypes.c_int
+    L.bpt_build_batch_graph.argtypes = [i32, i32, i32, vp, i32, vp, P(vp)]
+    L.bpt_graph_layout.restype = ctypes.c_int
+    L.bpt_graph_layout.argtypes = [vp, P(i32), P(i32), vp, vp]
     L.bpt_graph_info.restype = ctypes.c_int
     L.bpt_graph_info.argtypes = [vp, P(i32), P(i32), P(i32), P(i32), P(i64), P(i32), P(i32), P(i32)]
     L.bpt_graph_csr.restype = ctypes.c_int
@@ -144,13 +148,21 @@ def _stream_ptr() -> int:
 
 
 class Graph:
-    """Device-resident binary-partition graph (bpt_build_graph)."""
+    """Device-resident binary-partition graph (bpt_build_graph; with `lengths`, bpt_build_batch_graph)."""
 
-    def __init__(self, n: int, k: int, causal: bool):
+    def __init__(self, n: int, k: int, causal: bool, lengths=None):
         L = load_library()
         handle = ctypes.c_void_p()
-        _check(L.bpt_build_graph(int(n), int(k), int(bool(causal)), _stream_ptr(), ctypes.byref(handle)),
-               "bpt_build_graph(n=%d, k=%d, causal=%d)" % (n, k, causal))
+        if lengths is None:
+            _check(L.bpt_build_graph(int(n), int(k), int(bool(causal)), _stream_ptr(), ctypes.byref(handle)),
+                   "bpt_build_graph(n=%d, k=%d, causal=%d)" % (n, k, causal))
+        else:
+            lens = np.ascontiguousarray(lengths, dtype=np.int32)
+            if lens.ndim != 1:
+                raise ValueError("lengths must be one-dimensional")
+            _check(L.bpt_build_batch_graph(int(n), int(k), int(bool(causal)), lens.ctypes.data, int(lens.size), _stream_ptr(),
+                                           ctypes.byref(handle)),
+                   "bpt_build_batch_graph(n=%d, k=%d, causal=%d, batch=%d)" % (n, k, causal, lens.size))
         self._h = handle
         i32, i64 = ctypes.c_int32, ctypes.c_int64
         vals = [i32(), i32(), i32(), i32(), i64(), i32(), i32(), i32()]
@@ -158,6 +170,13 @@ class Graph:
         (self.n, self.k, causal_i, self.num_nodes, self.num_edges, self.num_levels, self.rel_width,
          self.ctx_levels) = [int(v.value) for v in vals]
         self.causal = bool(causal_i)
+        batch, n_tokens = i32(), i32()
+        _check(L.bpt_graph_layout(self._h, ctypes.byref(batch), ctypes.byref(n_tokens), None, None), "bpt_graph_layout")
+        self.batch, self.n_tokens = int(batch.value), int(n_tokens.value)
+        self.first_row = np.empty((self.num_levels, self.batch), dtype=np.int32)
+        self.row_count = np.empty((self.num_levels, self.batch), dtype=np.int32)
+        _check(L.bpt_graph_layout(self._h, None, None, self.first_row.ctypes.data, self.row_count.ctypes.data),
+               "bpt_graph_layout")
 
     @property
     def handle(self) -> ctypes.c_void_p:
@@ -212,6 +231,11 @@ def bpt_count_edges(n: int, k: int, causal: bool, length: int) -> int:
 
 def bpt_build_graph(n: int, k: int, causal: bool) -> Graph:
     return Graph(n, k, causal)
+
+
+def bpt_build_batch_graph(n: int, k: int, causal: bool, lengths) -> Graph:
+    """One graph for a batch of sequences of the given lengths, rows packed (see include/bpt.h)."""
+    return Graph(n, k, causal, lengths)
 
 
 def _shape_of(g: Graph, x: torch.Tensor, scale: Optional[float], seq_len: Optional[torch.Tensor] = None,

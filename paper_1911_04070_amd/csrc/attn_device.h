@@ -104,6 +104,11 @@ __device__ __forceinline__ int node_first_token(int id, int lg) {
     const int level = lg - (31 - __clz(x - 1));
     return (((2 << lg) >> level) - x) << level;
 }
+// whether a sequence of `len` tokens keeps `node`.  Without seq_len every row of the graph is a kept node (also
+// in the graph of a packed batch, whose rows are not the nodes of one tree).
+__device__ __forceinline__ bool node_kept(const AttnArgs& a, int node, int len) {
+    return !a.seq_len || node_first_token(node, a.lg) < len;
+}
 // The walk over (batch*head, tile) gives every XCD a contiguous share.  With sequences of
 // different lengths the shares are cut head-major (all batch entries of a head together), so that
 // every XCD gets the same mix of lengths instead of a few whole batch entries.

@@ -34,7 +34,7 @@ __device__ __forceinline__ void fwd_segment(const AttnArgs& a, const T* rel_s, r
     const int slot = lane >> 3, sub = lane & 7;
     const int lane_off = sub * 8 * (int)sizeof(T);
     const T* relg = static_cast<const T*>(a.rel) + sub * 8;
-    const bool row_kept = node_first_token(u, a.lg) < len;
+    const bool row_kept = node_kept(a, u, len);
     const uint32_t rowh = drop_row_hash(drop_bh_hash(a.drop_seed, bh), u);
 
     // indices two iterations ahead, rows one iteration ahead.  Lanes past the end of
@@ -71,7 +71,7 @@ __device__ __forceinline__ void fwd_segment(const AttnArgs& a, const T* rel_s, r
         vn = gather_row<T>(rV, c1, a.row_bytes, lane_off);
         eo += 32;
 
-        const bool valid = eb + slot < e1 && row_kept && node_first_token(cnow, a.lg) < len;
+        const bool valid = eb + slot < e1 && row_kept && node_kept(a, cnow, len);
         const float keep = a.drop_thr ? drop_scale(rowh, drop_edge_x(!SPAN, r0, cnow), a.drop_thr, a.drop_inv_keep) : 1.f;
         cnow = c1;
         float vv[8], d = 0.f;
@@ -254,7 +254,7 @@ __device__ __forceinline__ void bwd_q_segment(const AttnArgs& a, const T* rel_s,
     const int slot = lane >> 3, sub = lane & 7;
     const int lane_off = sub * 8 * (int)sizeof(T);
     const T* relg = static_cast<const T*>(a.rel) + sub * 8;
-    const bool row_kept = node_first_token(u, a.lg) < len;
+    const bool row_kept = node_kept(a, u, len);
     const uint32_t rowh = drop_row_hash(drop_bh_hash(a.drop_seed, bh), u);
 
     int eo = (e0 + slot) * 4;
@@ -295,7 +295,7 @@ __device__ __forceinline__ void bwd_q_segment(const AttnArgs& a, const T* rel_s,
         vn = gather_row<T>(rV, c1, a.row_bytes, lane_off);
 
         const bool inside = eb + slot < e1;
-        const bool valid = inside && row_kept && node_first_token(cnow, a.lg) < len;
+        const bool valid = inside && row_kept && node_kept(a, cnow, len);
         const float keep = a.drop_thr ? drop_scale(rowh, drop_edge_x(!SPAN, r0, cnow), a.drop_thr, a.drop_inv_keep) : 1.f;
         cnow = c1;
         float kk[8];
@@ -460,7 +460,7 @@ __global__ void __launch_bounds__(256) bwd_q_merge_kernel(const AttnArgs a, cons
     }
     const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
     a.dQ[base + (int64_t)u * a.sn + lane] = a.scale * (sa - dl * sb);
-    const bool kept = node_first_token(u, a.lg) < seq_length(a.seq_len, bh / a.H, a.n_tokens);
+    const bool kept = node_kept(a, u, seq_length(a.seq_len, bh / a.H, a.n_tokens));
     if (lane == 0) a.stat[(int64_t)bh * a.N + u] = make_float2(kept ? a.lse_r[(int64_t)bh * a.N + u] * kLog2e : kLseGone, dl);
 }
 
@@ -482,7 +482,7 @@ __device__ __forceinline__ void bwd_kv_segment(const AttnArgs& a, const T* rel_s
     for (int i = 0; i < 8; ++i) dk[i] = dv[i] = 0.f;
 
     // queries that are not kept carry kLseGone in `stat`; a key that is not kept has no edge at all
-    if (e1 > e0 && node_first_token(v, a.lg) < len) {
+    if (e1 > e0 && node_kept(a, v, len)) {
         int eo = (e0 + slot) * 4;
         const int u0 = buf_i32(rIa, eo);
         int unow = u0;   // query node of the rows in work
@@ -596,7 +596,7 @@ __global__ void __launch_bounds__(kThreads) rel_grad_kernel(const AttnArgs a) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int id0 = blockIdx.y * kDrelChunk;                // first id of this workgroup's chunk
-    const int blocks_per_bh = a.n_tokens / R;
+    const int blocks_per_bh = (a.n_tokens + R - 1) / R;   // the last block of a batch graph may be short
     const int total = a.BH * blocks_per_bh;
 
     float acc[kDrelIdsPerWave];
@@ -612,7 +612,12 @@ __global__ void __launch_bounds__(kThreads) rel_grad_kernel(const AttnArgs a) {
             for (int i = threadIdx.x; i < R * 8; i += blockDim.x) {
                 const int r = i >> 3, c = (i & 7) * 8;
                 float x[8];
-                load8(Qb + (int64_t)(row0 + r) * a.sn + c, x);
+                if (row0 + r < a.n_tokens) {
+                    load8(Qb + (int64_t)(row0 + r) * a.sn + c, x);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) x[j] = 0.f;
+                }
 #pragma unroll
                 for (int j = 0; j < 8; ++j) q_s[r * kD + c + j] = x[j];
             }
@@ -620,7 +625,7 @@ __global__ void __launch_bounds__(kThreads) rel_grad_kernel(const AttnArgs a) {
         __syncthreads();
         // scatter dS of every edge of the block's rows: one wavefront per row, lanes over edges
         const float2* wp_b = a.wp + (int64_t)bh * a.e_tok;
-        for (int r = wave; r < R; r += kWaves) {
+        for (int r = wave; r < R && row0 + r < a.n_tokens; r += kWaves) {
             const int u = row0 + r;
             const float delta = a.stat[(int64_t)bh * a.N + u].y;
             const int e1 = a.ptr[u + 1];

@@ -74,6 +74,9 @@ int check_shape(const bpt_graph* g, const bpt_shape_t* s) {
     if (s->stride_n < kD || (s->stride_n % 8) || (s->stride_h % 8) || (s->stride_b % 8)) return BPT_ERR_INVALID_ARG;
     if (s->stride_h < 0 || s->stride_b < 0) return BPT_ERR_INVALID_ARG;
     if (!(s->dropout_p >= 0.f && s->dropout_p < 1.f)) return BPT_ERR_INVALID_ARG;
+    // a batch graph carries the lengths itself; dropout masks are defined on the nodes of one tree
+    if (g->batch > 0 && s->seq_len) return BPT_ERR_INVALID_ARG;
+    if (g->batch > 0 && s->dropout_p > 0.f) return BPT_ERR_UNSUPPORTED;
     if ((int64_t)s->B * s->H > (int64_t)INT32_MAX / std::max(g->fwd.num_tiles, g->tr.num_tiles))
         return BPT_ERR_UNSUPPORTED;
     if ((int64_t)s->B * s->H * g->num_nodes > (int64_t)1 << 40) return BPT_ERR_UNSUPPORTED;
@@ -141,7 +144,7 @@ void fill_common(AttnArgs& a, const bpt_graph* g, const bpt_shape_t* s) {
     a.BH = s->B * s->H;
     a.H = s->H;
     a.N = g->num_nodes;
-    a.n_tokens = g->n;
+    a.n_tokens = g->n_tokens;
     a.scale = s->scale > 0.f ? s->scale : 0.125f;  // 1/sqrt(64)
     a.rel_rows = g->num_levels * g->rel_width;
     const int64_t es = s->dtype == BPT_BF16 ? 2 : 4;
@@ -450,14 +453,14 @@ int plan_bwd(const bpt_graph* g, const bpt_shape_t* s, BwdPlan* p) {
             }
         }
         p->drel_grid_y = p->drel_tile ? 1 : (p->drel_rows + kRgIds - 1) / kRgIds;
-        blocks = (int64_t)s->B * s->H * ((g->n + kRgRows - 1) / kRgRows);
+        blocks = (int64_t)s->B * s->H * ((g->n_tokens + kRgRows - 1) / kRgRows);
     } else {
         p->drel_ipw = p->drel_rows <= 64 ? 8 : p->drel_rows <= 128 ? 16 : 32;
         const int chunk = p->drel_ipw * kWaves;
-        p->drel_block = std::min(g->n, chunk > 128 ? 32 : 64);
+        p->drel_block = std::min(g->n_tokens, chunk > 128 ? 32 : 64);
         p->drel_lds = (size_t)p->drel_block * (chunk + kD) * sizeof(float);
         p->drel_grid_y = (p->drel_rows + chunk - 1) / chunk;
-        blocks = (int64_t)s->B * s->H * (g->n / p->drel_block);
+        blocks = (int64_t)s->B * s->H * ((g->n_tokens + p->drel_block - 1) / p->drel_block);
     }
     const int per_cu = (int)std::max<size_t>(1, std::min<size_t>(4, lim.lds_cu / p->drel_lds));
     p->drel_grid_x = (int)std::max<int64_t>(1, std::min<int64_t>(blocks, (int64_t)lim.cus * per_cu / p->drel_grid_y));

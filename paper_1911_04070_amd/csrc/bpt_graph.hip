@@ -358,6 +358,239 @@ __global__ void t_fill_spans(int n, int num_levels, int32_t e_tok, const int32_t
     t_rel[pos] = rel[e];
 }
 
+// ---- a batch of sequences of different lengths as one graph ----------------------------------
+// The disjoint union of the graphs of B sequences (sequence b: len_b <= n tokens on the tree over n, keeping
+// the nodes whose first token exists; an edge needs both of its nodes).  Rows are numbered level-major over
+// the batch: the tokens of sequence 0, of sequence 1, ..., then the level-1 nodes of sequence 0, of sequence 1,
+// and so on, so that token rows still come first and the tokens under a span are consecutive rows.
+// first_row[l * B + b] is the row of node (l, 0) of sequence b; tok_off = first_row of level 0, with the total
+// appended.  Level l of a sequence of len tokens keeps ceil(len / 2^l) nodes.
+struct SeqToken {
+    int b, t, len;
+};
+// sequence and position of packed token i: the last b with tok_off[b] <= i (empty sequences share their offset
+// with the next one and are skipped by that rule)
+__device__ inline SeqToken locate_token(const int32_t* __restrict__ tok_off, int B, int i) {
+    int lo = 0, hi = B;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (tok_off[mid] <= i)
+            lo = mid;
+        else
+            hi = mid;
+    }
+    return SeqToken{lo, i - tok_off[lo], tok_off[lo + 1] - tok_off[lo]};
+}
+
+// RightWalk on the kept nodes of a sequence of `len` tokens: the run is clipped to the nodes the level keeps,
+// and the alignment node joins only if it is kept.  len = 0: never alive.
+struct RightWalkLen {
+    int p, level, len;
+    __device__ RightWalkLen(int t, int len_) : p(t + 1), level(0), len(len_) {}
+    __device__ int count() const { return (len + (1 << level) - 1) >> level; }
+    __device__ bool alive() const { return p < count(); }
+    __device__ void run(int k, int& lo, int& hi) const {
+        const int c = count();
+        int e = (k - 1 > c - 1 - p) ? c - 1 : p + k - 1;
+        if ((e & 1) == 0 && e + 1 < c) e += 1;
+        lo = p;
+        hi = e;
+    }
+    __device__ void up(int hi) {
+        if (hi + 1 >= count()) {
+            p = INT32_MAX;  // exhausted
+        } else {
+            p = (hi + 1) >> 1;
+            ++level;
+        }
+    }
+};
+
+__global__ void batch_token_degree(int T, int k, int causal, int B, const int32_t* __restrict__ tok_off,
+                                   int32_t* __restrict__ deg, unsigned long long* __restrict__ total,
+                                   int32_t* __restrict__ max_levels) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    int d = 0, used = 0;
+    if (i < T) {
+        const SeqToken s = locate_token(tok_off, B, i);
+        d = 1;
+        LeftWalk L(s.t);
+        int lv = 0;
+        while (L.alive()) {
+            int lo, hi;
+            L.run(k, lo, hi);
+            d += hi - lo + 1;
+            L.up(lo);
+            ++lv;
+        }
+        used = lv;
+        RightWalkLen R(s.t, causal ? 0 : s.len);
+        lv = 0;
+        while (R.alive()) {
+            int lo, hi;
+            R.run(k, lo, hi);
+            d += hi - lo + 1;
+            R.up(hi);
+            ++lv;
+        }
+        used = max(used, lv);
+        deg[i] = d;
+    }
+    __shared__ unsigned long long s_sum[kScanThreads];
+    __shared__ int s_lv[kScanThreads];
+    s_sum[threadIdx.x] = (unsigned long long)d;
+    s_lv[threadIdx.x] = used;
+    __syncthreads();
+    for (int w = blockDim.x / 2; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) {
+            s_sum[threadIdx.x] += s_sum[threadIdx.x + w];
+            s_lv[threadIdx.x] = max(s_lv[threadIdx.x], s_lv[threadIdx.x + w]);
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        atomicAdd(total, s_sum[0]);
+        atomicMax(max_levels, s_lv[0]);
+    }
+}
+
+__global__ void batch_fill_tokens(int T, int k, int causal, int B, const int32_t* __restrict__ tok_off,
+                                  const int32_t* __restrict__ first_row, const int32_t* __restrict__ row_ptr,
+                                  int32_t* __restrict__ col, int32_t* __restrict__ rel) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= T) return;
+    const SeqToken s = locate_token(tok_off, B, i);
+    const int W = 2 * (k + 1) + 1, zero = k + 1;
+    int e = row_ptr[i];
+    LeftWalk L(s.t);
+    RightWalkLen R(s.t, causal ? 0 : s.len);
+    for (int j = 0; j == 0 || L.alive() || R.alive(); ++j) {
+        const int off = first_row[j * B + s.b];
+        if (L.alive()) {
+            int lo, hi;
+            L.run(k, lo, hi);
+            for (int x = lo; x <= hi; ++x) {
+                col[e] = off + x;
+                rel[e] = j * W + zero - (hi - x + 1);
+                ++e;
+            }
+            L.up(lo);
+        }
+        if (j == 0) {
+            col[e] = i;
+            rel[e] = zero;
+            ++e;
+        }
+        if (R.alive()) {
+            int lo, hi;
+            R.run(k, lo, hi);
+            for (int x = lo; x <= hi; ++x) {
+                col[e] = off + x;
+                rel[e] = j * W + zero + (x - lo + 1);
+                ++e;
+            }
+            R.up(hi);
+        }
+    }
+}
+
+// Affiliated edges: on every level above the tokens the kept spans of all sequences hold every token once,
+// in row order -- the T edges of a level are the tokens 0..T-1.  Span (l, m) of sequence b starts at token
+// m * 2^l of that sequence.
+__global__ void batch_fill_spans(int T, int k, int B, int num_levels, int num_nodes, int32_t e_tok,
+                                 const int32_t* __restrict__ tok_off, const int32_t* __restrict__ first_row,
+                                 int32_t* __restrict__ row_ptr, int32_t* __restrict__ col, int32_t* __restrict__ rel) {
+    const int64_t a = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t total = (int64_t)T * (num_levels - 1);
+    const int W = 2 * (k + 1) + 1, zero = k + 1;
+    if (a < total) {
+        const int lev = 1 + (int)(a / T);
+        col[e_tok + a] = (int)(a % T);
+        rel[e_tok + a] = lev * W + zero;
+    }
+    if (a < num_nodes - T) {
+        const int node = T + (int)a;
+        int lev = 1;
+        while (lev + 1 < num_levels && first_row[(lev + 1) * B] <= node) ++lev;
+        const int32_t* fr = first_row + lev * B;
+        int lo = 0, hi = B;
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (fr[mid] <= node)
+                lo = mid;
+            else
+                hi = mid;
+        }
+        const int64_t m = node - fr[lo];
+        row_ptr[node] = (int32_t)(e_tok + (int64_t)(lev - 1) * T + tok_off[lo] + (m << lev));
+    }
+    if (a == 0) row_ptr[num_nodes] = (int32_t)(e_tok + total);
+}
+
+// t_ranges for the packed batch: the neighbours of a token are those of its own sequence
+__global__ void batch_t_ranges(int T, int k, int causal, int B, const int32_t* __restrict__ tok_off,
+                               const int32_t* __restrict__ first_row, int32_t* __restrict__ last_l,
+                               int32_t* __restrict__ last_r, int32_t* __restrict__ min_l, int32_t* __restrict__ min_r) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= T) return;
+    const SeqToken s = locate_token(tok_off, B, i);
+    const bool has_prev = s.t > 0, has_next = s.t + 1 < s.len;
+    {
+        LeftWalk A(s.t), P(s.t - 1), N(s.t + 1);
+        for (int j = 0; A.alive(); ++j) {
+            const int off = first_row[j * B + s.b];
+            int lo, hi, plo = 0, phi = -1, nlo = 0, nhi = -1;
+            A.run(k, lo, hi);
+            const bool pa = has_prev && P.alive(), na = has_next && N.alive();
+            if (pa) P.run(k, plo, phi);
+            if (na) N.run(k, nlo, nhi);
+            for (int x = lo; x <= hi; ++x) {
+                if (!(pa && plo <= x && x <= phi)) min_r[off + x] = i;
+                if (!(na && nlo <= x && x <= nhi)) last_r[off + x] = i;
+            }
+            A.up(lo);
+            if (pa) P.up(plo);
+            if (na) N.up(nlo);
+        }
+    }
+    if (!causal) {
+        RightWalkLen A(s.t, s.len), P(s.t - 1, s.len), N(s.t + 1, s.len);
+        for (int j = 0; A.alive(); ++j) {
+            const int off = first_row[j * B + s.b];
+            int lo, hi, plo = 0, phi = -1, nlo = 0, nhi = -1;
+            A.run(k, lo, hi);
+            // every walk climbs one level per step until it dies, so the three are on level j together
+            const bool pa = has_prev && P.alive(), na = has_next && N.alive();
+            if (pa) P.run(k, plo, phi);
+            if (na) N.run(k, nlo, nhi);
+            for (int x = lo; x <= hi; ++x) {
+                if (!(pa && plo <= x && x <= phi)) min_l[off + x] = i;
+                if (!(na && nlo <= x && x <= nhi)) last_l[off + x] = i;
+            }
+            A.up(hi);
+            if (pa) P.up(phi);
+            if (na) N.up(nhi);
+        }
+    }
+}
+
+__global__ void batch_t_fill_spans(int T, int B, int num_levels, int32_t e_tok, const int32_t* __restrict__ tok_off,
+                                   const int32_t* __restrict__ first_row, const int32_t* __restrict__ rel,
+                                   const int32_t* __restrict__ t_ptr, const int32_t* __restrict__ cnt_l,
+                                   const int32_t* __restrict__ cnt_r, int32_t* __restrict__ t_src,
+                                   int32_t* __restrict__ t_eid, int32_t* __restrict__ t_rel) {
+    const int64_t a = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (a >= (int64_t)T * (num_levels - 1)) return;
+    const int lev = 1 + (int)(a / T);
+    const int i = (int)(a % T);
+    const SeqToken s = locate_token(tok_off, B, i);
+    const int32_t e = (int32_t)(e_tok + a);
+    const int pos = t_ptr[i] + cnt_l[i] + 1 + cnt_r[i] + (lev - 1);
+    t_src[pos] = first_row[lev * B + s.b] + (s.t >> lev);
+    t_eid[pos] = e;
+    t_rel[pos] = rel[e];
+}
+
 // ---- host helpers -------------------------------------------------------------
 struct DeviceBuf {  // frees on scope exit unless released
     void* p = nullptr;
@@ -406,8 +639,9 @@ int upload(const std::vector<T>& h, T** d) {
 // Cut rows into segments of at most kSeg edges and group consecutive segments
 // into tiles of about kTileWork work units.  Rows without edges still get one
 // (empty) segment so that their outputs are written.
-// Rows from `span_from` on are span rows: 8 consecutive ones of equal degree <= kSpan8MaxDeg
-// become one segment marked kPartSpan8 (pass the row count to disable).
+// Rows from `span_from` on are span rows: 8 consecutive ones of equal degree <= kSpan8MaxDeg, a power of two (a
+// span of a batch graph that a sequence's end cuts short has any degree), become one segment marked kPartSpan8
+// (pass the row count to disable).
 int make_schedule(const std::vector<int32_t>& ptr, int32_t first_row, int32_t span_from, Schedule& out) {
     const int32_t rows = (int32_t)ptr.size() - 1;
     std::vector<int32_t> seg_row, seg_begin, seg_part, tile_ptr, multi_row, multi_ptr;
@@ -420,7 +654,8 @@ int make_schedule(const std::vector<int32_t>& ptr, int32_t first_row, int32_t sp
     int32_t parts = 0;
     for (int32_t u = first_row; u < rows; ++u) {
         const int32_t b = ptr[u], deg = ptr[u + 1] - b;
-        if (u >= span_from && u + 8 <= rows && deg >= 2 && deg <= kSpan8MaxDeg && ptr[u + 8] - b == 8 * deg) {
+        if (u >= span_from && u + 8 <= rows && deg >= 2 && deg <= kSpan8MaxDeg && (deg & (deg - 1)) == 0 &&
+            ptr[u + 8] - b == 8 * deg) {
             bool same = true;
             for (int32_t x = 1; x < 8; ++x) same = same && ptr[u + x + 1] - ptr[u + x] == deg;
             if (same) {
@@ -495,6 +730,7 @@ int build(int32_t n, int32_t k, int32_t causal, hipStream_t st, bpt_graph* g) {
     const int num_levels = 32 - __builtin_clz((unsigned)n);  // log2(n) + 1
     const int num_nodes = 2 * n - 1;
     g->n = n;
+    g->n_tokens = n;
     g->k = k;
     g->causal = causal ? 1 : 0;
     g->num_nodes = num_nodes;
@@ -589,6 +825,124 @@ int build(int32_t n, int32_t k, int32_t causal, hipStream_t st, bpt_graph* g) {
         return rc;
     if (g->tiles.num_tiles > 0 && (rc = make_schedule(h_ptr, n, n, g->fwd_span))) return rc;
     return BPT_OK;
+}
+
+// The graph of a batch of sequences (see the kernels above): same steps as build(), no dense tiles -- the
+// attention calls run the gather kernels on it.
+int build_batch(int32_t n, int32_t k, int32_t causal, const int32_t* lengths, int32_t B, hipStream_t st, bpt_graph* g) {
+    const int num_levels = 32 - __builtin_clz((unsigned)n);
+    g->n = n;
+    g->k = k;
+    g->causal = causal ? 1 : 0;
+    g->num_levels = num_levels;
+    g->rel_width = 2 * (k + 1) + 1;
+    g->batch = B;
+    BPT_HIP(hipGetDevice(&g->device));
+    hipDeviceProp_t prop;
+    BPT_HIP(hipGetDeviceProperties(&prop, g->device));
+    g->num_cus = prop.multiProcessorCount;
+
+    // row numbering (host): level-major over the batch
+    g->first_row.assign((size_t)num_levels * B, 0);
+    g->row_count.assign((size_t)num_levels * B, 0);
+    int64_t row = 0;
+    for (int l = 0; l < num_levels; ++l)
+        for (int b = 0; b < B; ++b) {
+            const int64_t cnt = ((int64_t)lengths[b] + ((int64_t)1 << l) - 1) >> l;
+            g->first_row[(size_t)l * B + b] = (int32_t)row;
+            g->row_count[(size_t)l * B + b] = (int32_t)cnt;
+            row += cnt;
+            if (row > (1 << 23)) return BPT_ERR_UNSUPPORTED;
+        }
+    const int num_nodes = (int)row;
+    std::vector<int32_t> h_tok_off((size_t)B + 1);
+    for (int b = 0; b < B; ++b) h_tok_off[b] = g->first_row[b];
+    const int T = B > 0 ? g->first_row[B - 1] + g->row_count[B - 1] : 0;
+    h_tok_off[B] = T;
+    if (T < 1) return BPT_ERR_INVALID_ARG;
+    g->num_nodes = num_nodes;
+    g->n_tokens = T;
+
+    DeviceBuf tok_off, first_row, deg, counters, block_sums;
+    BPT_HIP(tok_off.alloc(sizeof(int32_t) * h_tok_off.size()));
+    BPT_HIP(first_row.alloc(sizeof(int32_t) * g->first_row.size()));
+    BPT_HIP(hipMemcpyAsync(tok_off.p, h_tok_off.data(), sizeof(int32_t) * h_tok_off.size(), hipMemcpyHostToDevice, st));
+    BPT_HIP(hipMemcpyAsync(first_row.p, g->first_row.data(), sizeof(int32_t) * g->first_row.size(), hipMemcpyHostToDevice, st));
+    BPT_HIP(deg.alloc(sizeof(int32_t) * (size_t)num_nodes));
+    BPT_HIP(counters.alloc(16));
+    BPT_HIP(block_sums.alloc(sizeof(int32_t) * kScanBlock));
+    BPT_HIP(hipMemsetAsync(counters.p, 0, 16, st));
+    const int tb = kScanThreads;
+    const int token_blocks = (T + tb - 1) / tb;
+    const int node_blocks = (num_nodes + tb - 1) / tb;
+
+    // 1. token degrees
+    hipLaunchKernelGGL(batch_token_degree, dim3(token_blocks), dim3(tb), 0, st, T, k, g->causal, B, tok_off.as<int32_t>(),
+                       deg.as<int32_t>(), counters.as<unsigned long long>(), counters.as<int32_t>() + 2);
+    BPT_HIP(hipGetLastError());
+    struct {
+        unsigned long long total;
+        int32_t maxlev, pad;
+    } h = {0, 0, 0};
+    BPT_HIP(hipMemcpyAsync(&h, counters.p, 16, hipMemcpyDeviceToHost, st));
+    BPT_HIP(hipStreamSynchronize(st));   // also: the host arrays above have been read
+    const int64_t e_tok = (int64_t)h.total;
+    const int64_t aff = (int64_t)T * (num_levels - 1);
+    const int64_t e_all = e_tok + aff;
+    if (e_all > INT32_MAX) return BPT_ERR_OVERFLOW;
+    g->num_edges = e_all;
+    g->num_token_edges = e_tok;
+    g->ctx_levels = std::max(1, (int)h.maxlev);
+
+    // 2. row_ptr, 3. fill
+    BPT_HIP(hipMalloc((void**)&g->row_ptr, sizeof(int32_t) * ((size_t)num_nodes + 1)));
+    BPT_HIP(hipMalloc((void**)&g->col, sizeof(int32_t) * (size_t)e_all));
+    BPT_HIP(hipMalloc((void**)&g->rel, sizeof(int32_t) * (size_t)e_all));
+    int rc = exclusive_scan(deg.as<int32_t>(), g->row_ptr, T, (int32_t)e_tok, block_sums.as<int32_t>(), st);
+    if (rc) return rc;
+    hipLaunchKernelGGL(batch_fill_tokens, dim3(token_blocks), dim3(tb), 0, st, T, k, g->causal, B, tok_off.as<int32_t>(),
+                       first_row.as<int32_t>(), g->row_ptr, g->col, g->rel);
+    const int64_t span_items = std::max<int64_t>(std::max<int64_t>(aff, num_nodes - T), 1);
+    hipLaunchKernelGGL(batch_fill_spans, dim3((unsigned)((span_items + tb - 1) / tb)), dim3(tb), 0, st, T, k, B, num_levels,
+                       num_nodes, (int32_t)e_tok, tok_off.as<int32_t>(), first_row.as<int32_t>(), g->row_ptr, g->col, g->rel);
+    BPT_HIP(hipGetLastError());
+
+    // 4. transposed adjacency
+    DeviceBuf cnt_l, cnt_r, min_l, min_r;
+    const size_t nb = sizeof(int32_t) * (size_t)num_nodes;
+    BPT_HIP(cnt_l.alloc(nb));
+    BPT_HIP(cnt_r.alloc(nb));
+    BPT_HIP(min_l.alloc(nb));
+    BPT_HIP(min_r.alloc(nb));
+    BPT_HIP(hipMalloc((void**)&g->t_ptr, sizeof(int32_t) * ((size_t)num_nodes + 1)));
+    BPT_HIP(hipMalloc((void**)&g->t_src, sizeof(int32_t) * (size_t)e_all));
+    BPT_HIP(hipMalloc((void**)&g->t_eid, sizeof(int32_t) * (size_t)e_all));
+    BPT_HIP(hipMalloc((void**)&g->t_rel, sizeof(int32_t) * (size_t)e_all));
+    hipLaunchKernelGGL(t_init, dim3(node_blocks), dim3(tb), 0, st, num_nodes, cnt_l.as<int32_t>(), cnt_r.as<int32_t>(),
+                       min_l.as<int32_t>(), min_r.as<int32_t>());
+    hipLaunchKernelGGL(batch_t_ranges, dim3(token_blocks), dim3(tb), 0, st, T, k, g->causal, B, tok_off.as<int32_t>(),
+                       first_row.as<int32_t>(), cnt_l.as<int32_t>(), cnt_r.as<int32_t>(), min_l.as<int32_t>(),
+                       min_r.as<int32_t>());
+    hipLaunchKernelGGL(t_degree, dim3(node_blocks), dim3(tb), 0, st, T, num_nodes, num_levels, cnt_l.as<int32_t>(),
+                       cnt_r.as<int32_t>(), min_l.as<int32_t>(), min_r.as<int32_t>(), deg.as<int32_t>());
+    BPT_HIP(hipGetLastError());
+    rc = exclusive_scan(deg.as<int32_t>(), g->t_ptr, num_nodes, (int32_t)e_all, block_sums.as<int32_t>(), st);
+    if (rc) return rc;
+    hipLaunchKernelGGL(t_fill_tokens, dim3(token_blocks), dim3(tb), 0, st, T, k, g->row_ptr, g->col, g->rel, g->t_ptr,
+                       cnt_l.as<int32_t>(), min_l.as<int32_t>(), min_r.as<int32_t>(), g->t_src, g->t_eid, g->t_rel);
+    if (aff > 0)
+        hipLaunchKernelGGL(batch_t_fill_spans, dim3((unsigned)((aff + tb - 1) / tb)), dim3(tb), 0, st, T, B, num_levels,
+                           (int32_t)e_tok, tok_off.as<int32_t>(), first_row.as<int32_t>(), g->rel, g->t_ptr,
+                           cnt_l.as<int32_t>(), cnt_r.as<int32_t>(), g->t_src, g->t_eid, g->t_rel);
+    BPT_HIP(hipGetLastError());
+
+    // 5. launch schedules
+    std::vector<int32_t> h_ptr((size_t)num_nodes + 1), h_tptr((size_t)num_nodes + 1);
+    BPT_HIP(hipMemcpyAsync(h_ptr.data(), g->row_ptr, sizeof(int32_t) * h_ptr.size(), hipMemcpyDeviceToHost, st));
+    BPT_HIP(hipMemcpyAsync(h_tptr.data(), g->t_ptr, sizeof(int32_t) * h_tptr.size(), hipMemcpyDeviceToHost, st));
+    BPT_HIP(hipStreamSynchronize(st));
+    if ((rc = make_schedule(h_ptr, 0, T, g->fwd))) return rc;
+    return make_schedule(h_tptr, 0, num_nodes, g->tr);
 }
 
 }  // namespace
@@ -761,6 +1115,48 @@ int bpt_build_graph(int32_t n, int32_t k, int32_t causal, void* stream, bpt_grap
         return rc;
     }
     *out = g;
+    return BPT_OK;
+}
+
+int bpt_build_batch_graph(int32_t n, int32_t k, int32_t causal, const int32_t* lengths, int32_t batch, void* stream,
+                          bpt_graph_t** out) {
+    if (!out) return BPT_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (n < 2 || k < 1 || !lengths || batch < 1) return BPT_ERR_INVALID_ARG;
+    if ((n & (n - 1)) != 0 || n > (1 << 22) || k > (1 << 20) || batch > (1 << 16)) return BPT_ERR_UNSUPPORTED;
+    for (int32_t b = 0; b < batch; ++b)
+        if (lengths[b] < 0 || lengths[b] > n) return BPT_ERR_INVALID_ARG;
+    bpt_graph* g = new (std::nothrow) bpt_graph();
+    if (!g) return BPT_ERR_ALLOC;
+    int rc;
+    try {
+        rc = bpt::build_batch(n, k, causal, lengths, batch, static_cast<hipStream_t>(stream), g);
+        void* scratch_ptr = nullptr;
+        if (rc == BPT_OK) rc = bpt::static_scratch(g->device, &scratch_ptr);
+    } catch (const std::bad_alloc&) {
+        rc = BPT_ERR_ALLOC;
+    }
+    if (rc != BPT_OK) {
+        bpt_graph_destroy(g);
+        return rc;
+    }
+    *out = g;
+    return BPT_OK;
+}
+
+int bpt_graph_layout(const bpt_graph_t* g, int32_t* batch, int32_t* n_tokens, int32_t* first_row, int32_t* row_count) {
+    if (!g) return BPT_ERR_INVALID_ARG;
+    if (batch) *batch = g->batch > 0 ? g->batch : 1;
+    if (n_tokens) *n_tokens = g->n_tokens;
+    if (g->batch > 0) {
+        if (first_row) std::copy(g->first_row.begin(), g->first_row.end(), first_row);
+        if (row_count) std::copy(g->row_count.begin(), g->row_count.end(), row_count);
+    } else {
+        for (int l = 0; l < g->num_levels; ++l) {
+            if (first_row) first_row[l] = (int32_t)bpt::level_offset(g->n, l);
+            if (row_count) row_count[l] = g->n >> l;
+        }
+    }
     return BPT_OK;
 }
 

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "bpt.h"
 
 namespace bpt {
@@ -81,6 +83,9 @@ struct KeyTiles {
 struct bpt_graph {
     int32_t n = 0, k = 0, causal = 0;
     int32_t num_nodes = 0, num_levels = 0, rel_width = 0, ctx_levels = 0;
+    int32_t n_tokens = 0;         // token rows (they come first): n, or the tokens of all sequences of a batch graph
+    int32_t batch = 0;            // sequences packed into this graph (bpt_build_batch_graph); 0: the graph of one sequence
+    std::vector<int32_t> first_row, row_count;   // batch graph: [level][sequence] first node row and node count
     int64_t num_edges = 0;
     int64_t num_token_edges = 0;  // edges of token rows: they come first in the CSR
     int device = 0;

@@ -772,6 +772,7 @@ int bpt_layer_bwd(const bpt_graph_t* g, int32_t B, int32_t H, float scale, const
 
 size_t bpt_stack_fwd_workspace(const bpt_graph_t* g, int32_t B, int32_t H, int32_t d_ff, int32_t num_layers) {
     if (!g || B < 1 || H < 1 || d_ff < 8 || num_layers < 1 || num_layers > kMaxStackLayers) return 0;
+    if (g->batch > 0) return SIZE_MAX;   // embeddings and readout are laid out for the tree of one sequence
     if (bpt_layer_fwd_workspace(g, B, H, d_ff) == SIZE_MAX) return SIZE_MAX;
     return stack_buffers(g, B, H, d_ff, num_layers).total;
 }
@@ -781,7 +782,7 @@ int bpt_stack_fwd(const bpt_graph_t* g, int32_t B, int32_t H, int32_t num_layers
                   size_t workspace_bytes, void* stream) {
     if (!g || !rel || !E || !p || (!root && !tokens) || !workspace || B < 1 || H < 1 || num_layers < 1)
         return BPT_ERR_INVALID_ARG;
-    if (num_layers > kMaxStackLayers) return BPT_ERR_UNSUPPORTED;
+    if (num_layers > kMaxStackLayers || g->batch > 0) return BPT_ERR_UNSUPPORTED;
     for (int l = 0; l < num_layers; ++l) {
         if (!rel[l]) return BPT_ERR_INVALID_ARG;
         if (p[l].d_ff != p[0].d_ff) return BPT_ERR_UNSUPPORTED;   // one workspace size serves every layer
@@ -814,6 +815,7 @@ int bpt_stack_fwd(const bpt_graph_t* g, int32_t B, int32_t H, int32_t num_layers
 
 size_t bpt_stack_bwd_workspace(const bpt_graph_t* g, int32_t B, int32_t H, int32_t d_ff) {
     if (!g || B < 1 || H < 1 || d_ff < 8) return 0;
+    if (g->batch > 0) return SIZE_MAX;
     const size_t layer = bpt_layer_bwd_workspace(g, B, H, d_ff);
     if (layer == SIZE_MAX) return SIZE_MAX;
     return layer ? 2 * align_up((size_t)B * g->num_nodes * H * kD * 2) + layer : 0;
@@ -826,7 +828,7 @@ int bpt_stack_bwd(const bpt_graph_t* g, int32_t B, int32_t H, int32_t num_layers
     if (!g || !rel || !p || !fwd_workspace || (!d_root && !d_tokens) || !dE || !d_rel || !grads || !workspace || B < 1 ||
         H < 1 || num_layers < 1)
         return BPT_ERR_INVALID_ARG;
-    if (num_layers > kMaxStackLayers) return BPT_ERR_UNSUPPORTED;
+    if (num_layers > kMaxStackLayers || g->batch > 0) return BPT_ERR_UNSUPPORTED;
     for (int l = 0; l < num_layers; ++l) {
         if (!rel[l] || !d_rel[l]) return BPT_ERR_INVALID_ARG;
         if (p[l].d_ff != p[0].d_ff) return BPT_ERR_UNSUPPORTED;
