@@ -86,6 +86,8 @@ def parse():
     ap.add_argument("--zero-unkept", action="store_true",
                     help="workloads with sequences of different lengths: zero-fill the rows of nodes a sequence does not "
                          "keep (the default leaves them unwritten, bpt_shape_t.leave_unkept)")
+    ap.add_argument("--bf16-grads", action="store_true",
+                    help="dQ, dK, dV rounded to bf16 by the backward (bpt_shape_t.grad_dtype) instead of fp32")
     ap.add_argument("--packed", action="store_true",
                     help="workloads with sequences of different lengths: one graph for the whole batch with rows only for "
                          "the nodes that exist (bpt_build_batch_graph) instead of the padded trees")
@@ -357,7 +359,10 @@ def main():
     Q, K, V, R, dO = dev["Q"], dev["K"], dev["V"], dev["Rel"], dev["dO"]
     out = torch.empty_like(Q)
     lse = torch.empty(Q.shape[:3], dtype=torch.float32, device="cuda")
-    grads = tuple(torch.empty(Q.shape, dtype=torch.float32, device="cuda") for _ in range(3)) + (
+    if args.bf16_grads and w.dtype != "bf16":
+        sys.exit("--bf16-grads is for the bf16 workloads")
+    gdt = torch.bfloat16 if args.bf16_grads else torch.float32
+    grads = tuple(torch.empty(Q.shape, dtype=gdt, device="cuda") for _ in range(3)) + (
         torch.empty(R.shape, dtype=torch.float32, device="cuda"),)
     fws, bws = bpt.workspace_bytes(g, Q, w.scale)
     ws_f = torch.empty(max(fws, 256), dtype=torch.uint8, device="cuda")
@@ -457,7 +462,8 @@ def main():
     alg_bytes["bwd_q_kernel"] = gather * (edge_inst - (tok_inst if "bwd_q_tile_kernel" in kernel_ms else 0) - (
         span_inst if "bwd_q_span_tile_kernel" in kernel_ms else 0))
     esz = 2 if w.dtype == "bf16" else 4
-    row, frow = w.D * esz, w.D * 4                            # a row of a tensor; a row of an fp32 gradient
+    gsz = 2 if args.bf16_grads else 4
+    row, frow = w.D * esz, w.D * gsz                          # a row of a tensor; a row of a gradient (fp32 unless --bf16-grads)
     # node rows per (batch, head), scaled by the fill of a batch of different lengths (the kept nodes)
     n_tok, n_span, n_all = w.n * fill, (w.n - 1) * fill, g.num_nodes * fill
     keys_tok = len(np.unique(col_h[:e_tok_graph])) * fill     # nodes some token row attends to
@@ -488,11 +494,11 @@ def main():
     # writes out, lse; the backward reads Q, K, V, dout, lse and writes dQ, dK, dV (fp32) -- no workspace traffic
     compulsory = tensor * esz * 4 + bh * n_all * 4
     if w.backward:
-        compulsory += tensor * esz * 4 + bh * n_all * 4 + 3 * tensor * 4
+        compulsory += tensor * esz * 4 + bh * n_all * 4 + 3 * tensor * gsz
     # measured HBM traffic (rocprofv3 counters, profiles/hbm_traffic.txt) -- only if taken on these kernel sources
     per_kernel, measured_on = measured_traffic(w.name)
     sources = kernel_source_hash()
-    fresh = bool(per_kernel) and measured_on == sources and args.dropout == 0
+    fresh = bool(per_kernel) and measured_on == sources and args.dropout == 0 and not args.bf16_grads
     traffic = step_traffic = None
     if fresh:
         if dominant in per_kernel:
@@ -582,7 +588,7 @@ def main():
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "n": w.n, "k": w.k, "causal": w.causal, "batch": w.B, "heads": w.H,
                    "head_dim": w.D, "nodes": g.num_nodes, "edges": g.num_edges, "edge_instances": edge_inst,
-                   "backward": w.backward, "dropout": args.dropout, "unkept_rows": ("unwritten" if leave else "zero-filled") if lengths is not None else None,
+                   "backward": w.backward, "dropout": args.dropout, "gradients": "bf16" if args.bf16_grads else "fp32", "unkept_rows": ("unwritten" if leave else "zero-filled") if lengths is not None else None,
                    "lengths": ([int(v) for v in lengths] if lengths is not None else None)},
         "graph_build_ms": round(build_ms, 3),
         "edges_per_s_incl_build": round(edge_inst / ((ms_per_step + build_ms) * 1e-3), 1),

@@ -93,6 +93,11 @@ typedef struct {
                              not keep are left unwritten (they hold whatever the buffers held) instead of being
                              zero-filled, so that the time and the bytes written follow the tokens that exist
                              rather than the padded size.  Rows of kept nodes and d_rel are the same either way. */
+    int32_t grad_dtype;   /* bpt_dtype_t of dQ, dK, dV: BPT_F32 (0, the default) or, with dtype = BPT_BF16, BPT_BF16:
+                             the backward then writes the three gradients rounded to bf16 (round to nearest even,
+                             from the same fp32 sums), with the tensor strides counted in bf16 elements -- half
+                             the bytes written, and gradients that feed a bf16 GEMM need no cast.  d_rel stays
+                             fp32.  Any other combination: BPT_ERR_INVALID_ARG. */
 } bpt_shape_t;
 
 /* Sec. 3.2 + Algorithm 1.  Builds, on the current device, the graph of a
@@ -204,15 +209,16 @@ int bpt_attn_fwd_static(const bpt_graph_t* g, const bpt_shape_t* s, const void* 
  *   dK_v = scale * sum_{e -> v} dS_e q_u        dV_v = sum_{e -> v} p_e dout_u
  *   d_rel[id] = scale * sum over batch, head and edges with id_e = id of dS_e q_u
  * lse is the forward's result; the forward's `out` is not needed (delta is
- * recomputed in fp32 from p and dP).  dQ, dK, dV (fp32, the tensor strides) and
+ * recomputed in fp32 from p and dP).  dQ, dK, dV (fp32, or bf16 with
+ * bpt_shape_t.grad_dtype; the tensor strides, in elements) and
  * d_rel (fp32, contiguous [num_levels][W][D]) are overwritten.  No atomics are
  * used anywhere: dK and dV are reduced over the transposed adjacency and d_rel as
  * a dense contraction over blocks of token rows, so all four gradients are
  * run-to-run identical.  workspace: device scratch of at least
  * bpt_attn_bwd_workspace bytes. */
 int bpt_attn_bwd(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q, const void* K,
-                 const void* V, const void* rel, const float* lse, const void* dout, float* dQ,
-                 float* dK, float* dV, float* d_rel, void* workspace, size_t workspace_bytes,
+                 const void* V, const void* rel, const float* lse, const void* dout, void* dQ,
+                 void* dK, void* dV, float* d_rel, void* workspace, size_t workspace_bytes,
                  void* stream);
 
 /* The two stages of bpt_attn_bwd, callable on their own (same workspace, same
@@ -222,11 +228,11 @@ int bpt_attn_bwd(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q, cons
  * second. */
 int bpt_attn_bwd_query_side(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q,
                             const void* K, const void* V, const void* rel, const float* lse,
-                            const void* dout, float* dQ, float* d_rel, void* workspace,
+                            const void* dout, void* dQ, float* d_rel, void* workspace,
                             size_t workspace_bytes, void* stream);
 int bpt_attn_bwd_key_side(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q,
                           const void* K, const void* V, const void* rel, const float* lse,
-                          const void* dout, float* dK, float* dV, void* workspace,
+                          const void* dout, void* dK, void* dV, void* workspace,
                           size_t workspace_bytes, void* stream);
 
 /* For benchmarks and tuning (not part of the paper's method): while enabled, every

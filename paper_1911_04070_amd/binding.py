@@ -34,7 +34,7 @@ class BptShape(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("D", ctypes.c_int32), ("dtype", ctypes.c_int32),
                 ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64), ("stride_n", ctypes.c_int64),
                 ("scale", ctypes.c_float), ("seq_len", ctypes.c_void_p), ("dropout_p", ctypes.c_float),
-                ("dropout_seed", ctypes.c_uint32), ("leave_unkept", ctypes.c_int32)]
+                ("dropout_seed", ctypes.c_uint32), ("leave_unkept", ctypes.c_int32), ("grad_dtype", ctypes.c_int32)]
 
 
 class BptLayerParams(ctypes.Structure):
@@ -239,7 +239,7 @@ def bpt_build_batch_graph(n: int, k: int, causal: bool, lengths) -> Graph:
 
 
 def _shape_of(g: Graph, x: torch.Tensor, scale: Optional[float], seq_len: Optional[torch.Tensor] = None,
-              dropout: Optional[Tuple[float, int]] = None, leave_unkept: bool = False) -> BptShape:
+              dropout: Optional[Tuple[float, int]] = None, leave_unkept: bool = False, bf16_grads: bool = False) -> BptShape:
     if x.dim() != 4 or x.shape[2] != g.num_nodes:
         raise ValueError("expected a [B,H,N=%d,D] tensor, got %s" % (g.num_nodes, tuple(x.shape)))
     if x.stride(3) != 1:
@@ -259,7 +259,7 @@ def _shape_of(g: Graph, x: torch.Tensor, scale: Optional[float], seq_len: Option
         lens = seq_len.data_ptr()
     return BptShape(B, H, D, dt, x.stride(0), x.stride(1), x.stride(2), float(scale) if scale else 0.0, lens,
                     float(dropout[0]) if dropout else 0.0, (int(dropout[1]) & 0xFFFFFFFF) if dropout else 0,
-                    1 if leave_unkept else 0)
+                    1 if leave_unkept else 0, BPT_BF16 if bf16_grads else BPT_F32)
 
 
 def _same_layout(ref: torch.Tensor, *others: torch.Tensor) -> None:
@@ -345,11 +345,16 @@ def _check_bwd_inputs(g, shp, Q, K, V, rel, lse, dout):
         raise ValueError("lse must be contiguous fp32 [B,H,N] on the tensors' device")
 
 
-def _check_grad(Q, *grads) -> None:
+def _check_grad(Q, *grads) -> bool:
+    """The gradients share Q's layout and are all fp32 or, for bf16 tensors, all bf16; returns whether they are bf16."""
+    bf = grads[0].dtype == torch.bfloat16
     for t in grads:
-        if t.dtype != torch.float32:
-            raise ValueError("dQ, dK, dV must be float32")
+        if t.dtype != (torch.bfloat16 if bf else torch.float32):
+            raise ValueError("dQ, dK, dV must all be float32, or all bfloat16")
+    if bf and Q.dtype != torch.bfloat16:
+        raise ValueError("bfloat16 gradients need bfloat16 tensors")
     _same_layout(Q, *grads)
+    return bf
 
 
 def _check_d_rel(g, shp, Q, d_rel) -> None:
@@ -367,17 +372,17 @@ def _check_bwd_workspace(L, g, shp, workspace) -> int:
     return ws_bytes
 
 
-def _bwd_prepare(g, Q, K, V, rel, lse, dout, scale, grads, workspace, seq_len=None, dropout=None, leave_unkept=False):
+def _bwd_prepare(g, Q, K, V, rel, lse, dout, scale, grads, workspace, seq_len=None, dropout=None, leave_unkept=False,
+                 bf16_grads=False):
     L = load_library()
-    shp = _shape_of(g, Q, scale, seq_len, dropout, leave_unkept)
-    _check_bwd_inputs(g, shp, Q, K, V, rel, lse, dout)
     if grads is None:
-        dQ, dK, dV = (torch.empty_strided(Q.shape, Q.stride(), dtype=torch.float32, device=Q.device)
-                      for _ in range(3))
-        d_rel = torch.empty((g.num_levels, g.rel_width, shp.D), dtype=torch.float32, device=Q.device)
+        gdt = torch.bfloat16 if bf16_grads else torch.float32
+        dQ, dK, dV = (torch.empty_strided(Q.shape, Q.stride(), dtype=gdt, device=Q.device) for _ in range(3))
+        d_rel = torch.empty((g.num_levels, g.rel_width, Q.shape[3]), dtype=torch.float32, device=Q.device)
     else:
         dQ, dK, dV, d_rel = grads
-    _check_grad(Q, dQ, dK, dV)
+    shp = _shape_of(g, Q, scale, seq_len, dropout, leave_unkept, _check_grad(Q, dQ, dK, dV))
+    _check_bwd_inputs(g, shp, Q, K, V, rel, lse, dout)
     _check_d_rel(g, shp, Q, d_rel)
     if workspace is None:
         need = _need(int(L.bpt_attn_bwd_workspace(g.handle, ctypes.byref(shp))), "bpt_attn_bwd_workspace")
@@ -388,10 +393,12 @@ def _bwd_prepare(g, Q, K, V, rel, lse, dout, scale, grads, workspace, seq_len=No
 
 def bpt_attn_bwd(g: Graph, Q, K, V, rel, lse, dout, scale: Optional[float] = None,
                  grads: Optional[Tuple[torch.Tensor, ...]] = None, workspace: Optional[torch.Tensor] = None,
-                 seq_len: Optional[torch.Tensor] = None, dropout: Optional[Tuple[float, int]] = None, leave_unkept: bool = False):
-    """dQ, dK, dV, d_rel (all fp32) = gradient of eq. (8) given dout and the forward's lse (and its dropout)."""
+                 seq_len: Optional[torch.Tensor] = None, dropout: Optional[Tuple[float, int]] = None, leave_unkept: bool = False,
+                 bf16_grads: bool = False):
+    """dQ, dK, dV, d_rel = gradient of eq. (8) given dout and the forward's lse (and its dropout).  All fp32; with
+    bf16_grads (or bf16 tensors passed in `grads`) dQ, dK, dV are rounded to bf16 (bpt_shape_t.grad_dtype)."""
     L, shp, (dQ, dK, dV, d_rel), ws, ws_bytes = _bwd_prepare(g, Q, K, V, rel, lse, dout, scale, grads, workspace,
-                                                             seq_len, dropout, leave_unkept)
+                                                             seq_len, dropout, leave_unkept, bf16_grads)
     _check(L.bpt_attn_bwd(g.handle, ctypes.byref(shp), Q.data_ptr(), K.data_ptr(), V.data_ptr(), rel.data_ptr(),
                           lse.data_ptr(), dout.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(),
                           d_rel.data_ptr(), ws.data_ptr(), ws_bytes, _stream_ptr()), "bpt_attn_bwd")
@@ -403,9 +410,8 @@ def bpt_attn_bwd_query_side(g: Graph, Q, K, V, rel, lse, dout, dQ, d_rel, worksp
                             dropout: Optional[Tuple[float, int]] = None, leave_unkept: bool = False):
     """First stage of the backward: dQ, d_rel, and delta into the workspace."""
     L = load_library()
-    shp = _shape_of(g, Q, scale, seq_len, dropout, leave_unkept)
+    shp = _shape_of(g, Q, scale, seq_len, dropout, leave_unkept, _check_grad(Q, dQ))
     _check_bwd_inputs(g, shp, Q, K, V, rel, lse, dout)
-    _check_grad(Q, dQ)
     _check_d_rel(g, shp, Q, d_rel)
     _check_bwd_workspace(L, g, shp, workspace)
     _check(L.bpt_attn_bwd_query_side(g.handle, ctypes.byref(shp), Q.data_ptr(), K.data_ptr(), V.data_ptr(),
@@ -419,9 +425,8 @@ def bpt_attn_bwd_key_side(g: Graph, Q, K, V, rel, lse, dout, dK, dV, workspace, 
                           seq_len: Optional[torch.Tensor] = None, dropout: Optional[Tuple[float, int]] = None, leave_unkept: bool = False):
     """Second stage of the backward: dK, dV (reads delta from the workspace)."""
     L = load_library()
-    shp = _shape_of(g, Q, scale, seq_len, dropout, leave_unkept)
+    shp = _shape_of(g, Q, scale, seq_len, dropout, leave_unkept, _check_grad(Q, dK, dV))
     _check_bwd_inputs(g, shp, Q, K, V, rel, lse, dout)
-    _check_grad(Q, dK, dV)
     _check_bwd_workspace(L, g, shp, workspace)
     _check(L.bpt_attn_bwd_key_side(g.handle, ctypes.byref(shp), Q.data_ptr(), K.data_ptr(), V.data_ptr(),
                                    rel.data_ptr(), lse.data_ptr(), dout.data_ptr(), dK.data_ptr(), dV.data_ptr(),

@@ -49,6 +49,7 @@ struct AttnArgs {
     uint32_t drop_thr, drop_seed;
     float drop_inv_keep;    // 1 / (1 - p)
     int32_t* queue;         // backward workspace: task counters of the key-tile kernel
+    int32_t grad_bf16;      // dQ, dK, dV leave rounded to bf16 (the three pointers then address bf16 elements)
 };
 
 // ---- dropout on the attention weights ---------------------------------------------------
@@ -323,6 +324,28 @@ __device__ __forceinline__ V load_once16(const void* p) {
 __device__ __forceinline__ void store_once(float4* p, float4 v) {
     typedef float vec4 __attribute__((ext_vector_type(4)));
     __builtin_nontemporal_store(vec4{v.x, v.y, v.z, v.w}, reinterpret_cast<vec4*>(p));
+}
+// Gradient rows (dQ, dK, dV) leave as fp32 or, on request, rounded to bf16 (round to nearest even): `tensor` is
+// the caller's pointer, `elem` an element offset (strides count elements of either type), and with as_bf16 the
+// pointer addresses bf16 elements.  as_bf16 is the same in all lanes.
+__device__ __forceinline__ void store_grad(float* tensor, int64_t elem, float v, bool as_bf16) {
+    if (as_bf16)
+        store_once(reinterpret_cast<bf16_t*>(tensor) + elem, (bf16_t)to_bf16_bits(v));
+    else
+        store_once(tensor + elem, v);
+}
+// four consecutive elements (elem a multiple of 4)
+__device__ __forceinline__ void store_grad4(float* tensor, int64_t elem, float4 v, bool as_bf16) {
+    if (as_bf16) {
+        typedef uint32_t vec2 __attribute__((ext_vector_type(2)));
+        const vec2 w = {to_bf16_bits(v.x) | (to_bf16_bits(v.y) << 16), to_bf16_bits(v.z) | (to_bf16_bits(v.w) << 16)};
+        __builtin_nontemporal_store(w, reinterpret_cast<vec2*>(reinterpret_cast<bf16_t*>(tensor) + elem));
+    } else {
+        store_once(reinterpret_cast<float4*>(tensor + elem), v);
+    }
+}
+__device__ __forceinline__ float load_grad(const float* tensor, int64_t elem, bool as_bf16) {
+    return as_bf16 ? __uint_as_float((uint32_t)reinterpret_cast<const bf16_t*>(tensor)[elem] << 16) : tensor[elem];
 }
 
 }  // namespace

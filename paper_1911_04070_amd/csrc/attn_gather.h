@@ -341,7 +341,7 @@ __device__ __forceinline__ void bwd_q_segment(const AttnArgs& a, const T* rel_s,
     if (part < 0) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) A[i] -= dl * Bv[i];
-        a.dQ[base + (int64_t)u * a.sn + col] = a.scale * reduce_slots8(A, lane);
+        store_grad(a.dQ, base + (int64_t)u * a.sn + col, a.scale * reduce_slots8(A, lane), a.grad_bf16);
         if (lane == 0) a.stat[(int64_t)bh * a.N + u] = make_float2(row_kept ? lse2 : kLseGone, dl);
     } else {
         float* dst = a.part + ((int64_t)bh * a.num_part + part) * kQPartStride;
@@ -404,7 +404,8 @@ __device__ __forceinline__ void bwd_q_span8(const AttnArgs& a, rsrc_t rK, rsrc_t
     }
 #pragma unroll
     for (int x = 0; x < 8; ++x) A[x] = a.scale * (A[x] - dl * Bv[x]);
-    store8(a.dQ + base + (int64_t)u * a.sn + sub * 8, A);
+    store_grad4(a.dQ, base + (int64_t)u * a.sn + sub * 8, make_float4(A[0], A[1], A[2], A[3]), a.grad_bf16);
+    store_grad4(a.dQ, base + (int64_t)u * a.sn + sub * 8 + 4, make_float4(A[4], A[5], A[6], A[7]), a.grad_bf16);
     if (sub == 0) a.stat[(int64_t)bh * a.N + u] = make_float2(tok0 < len ? lse2 : kLseGone, dl);
 }
 
@@ -459,7 +460,7 @@ __global__ void __launch_bounds__(256) bwd_q_merge_kernel(const AttnArgs a, cons
         dl += src[2 * kD];
     }
     const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
-    a.dQ[base + (int64_t)u * a.sn + lane] = a.scale * (sa - dl * sb);
+    store_grad(a.dQ, base + (int64_t)u * a.sn + lane, a.scale * (sa - dl * sb), a.grad_bf16);
     const bool kept = node_kept(a, u, seq_length(a.seq_len, bh / a.H, a.n_tokens));
     if (lane == 0) a.stat[(int64_t)bh * a.N + u] = make_float2(kept ? a.lse_r[(int64_t)bh * a.N + u] * kLog2e : kLseGone, dl);
 }
@@ -538,8 +539,8 @@ __device__ __forceinline__ void bwd_kv_segment(const AttnArgs& a, const T* rel_s
     const float tk = reduce_slots8(dk, lane), tv = reduce_slots8(dv, lane);
     const int col = sub * 8 + slot_elem(lane);
     if (part < 0) {
-        a.dK[base + (int64_t)v * a.sn + col] = tk * a.scale;
-        a.dV[base + (int64_t)v * a.sn + col] = tv;
+        store_grad(a.dK, base + (int64_t)v * a.sn + col, tk * a.scale, a.grad_bf16);
+        store_grad(a.dV, base + (int64_t)v * a.sn + col, tv, a.grad_bf16);
     } else {
         float* dst = a.part + ((int64_t)bh * a.num_part + part) * (2 * kD);
         dst[col] = tk * a.scale;

@@ -37,6 +37,7 @@ struct KeyArgs {
     int32_t num_tasks, num_part, num_chunks, nb_pad, W, zero;
     const int32_t* seq_len;   // [B] tokens of every sequence, or null
     int32_t leave_unkept;     // rows of nodes a shorter sequence does not keep: left unwritten instead of zero-filled
+    int32_t grad_bf16;        // dK, dV leave rounded to bf16
     int32_t n;
     uint32_t drop_thr, drop_seed;   // dropout on the attention weights (DROP variants)
     float drop_inv_keep;
@@ -314,20 +315,30 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyA
                 o_s[(4 * g + r) * kKvOutStride + kD + 16 * f + j] = dv[f][r];
             }
         wave_lds_sync();
+        if (part < 0 && a.grad_bf16) {   // rounded to bf16: 8 bytes per lane
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int idx = lane + 64 * i, key = idx >> 5, q4 = (idx & 31) * 4;
-            if (key < nkeys) {
-                const float4 v = *reinterpret_cast<const float4*>(o_s + key * kKvOutStride + q4);
-                float* dst;
-                if (part < 0)
-                    dst = (q4 < kD ? a.dK + q4 : a.dV + (q4 - kD)) + base + (int64_t)(node0 + key) * a.sn;
-                else
-                    dst = a.part + (((int64_t)bh * a.num_part + part) * 16 + key) * (2 * kD) + q4;
-                if (part < 0)
-                    store_once(reinterpret_cast<float4*>(dst), v);
-                else   // the merge kernel reads the partial sums
-                    *reinterpret_cast<float4*>(dst) = v;
+            for (int i = 0; i < 8; ++i) {
+                const int idx = lane + 64 * i, key = idx >> 5, q4 = (idx & 31) * 4;
+                if (key < nkeys)
+                    store_grad4(q4 < kD ? a.dK : a.dV, base + (int64_t)(node0 + key) * a.sn + (q4 & (kD - 1)),
+                                *reinterpret_cast<const float4*>(o_s + key * kKvOutStride + q4), true);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int idx = lane + 64 * i, key = idx >> 5, q4 = (idx & 31) * 4;
+                if (key < nkeys) {
+                    const float4 v = *reinterpret_cast<const float4*>(o_s + key * kKvOutStride + q4);
+                    float* dst;
+                    if (part < 0)
+                        dst = (q4 < kD ? a.dK + q4 : a.dV + (q4 - kD)) + base + (int64_t)(node0 + key) * a.sn;
+                    else
+                        dst = a.part + (((int64_t)bh * a.num_part + part) * 16 + key) * (2 * kD) + q4;
+                    if (part < 0)
+                        store_once(reinterpret_cast<float4*>(dst), v);
+                    else   // the merge kernel reads the partial sums
+                        *reinterpret_cast<float4*>(dst) = v;
+                }
             }
         }
         wave_lds_sync();
@@ -346,7 +357,8 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyA
 // bias of (query, id) is not staged through LDS: the product Q_chunk x Rel_sel^T leaves bias[query 4g + r][id j]
 // in lane (g, j), register r, and the lane that needs it reads it from there (ds_bpermute), which makes room
 // for the staging area.
-template <int NBC, bool DROP>
+// G16: dK and dV leave rounded to bf16 (a compile-time switch: the stores sit inside the pipelined loop)
+template <int NBC, bool DROP, bool G16>
 __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_chain_kernel(const KeyArgs a) {
     static_assert(NBC == 1 || NBC == 2, "the bias is looked up across the 16 lanes of a group, for up to two chunks of ids");
     extern __shared__ __align__(16) unsigned char smem[];
@@ -456,6 +468,16 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_chain_kernel(const Key
         bool staged = false;
         int st_node0 = 0, st_nkeys = 0;
         auto store_staged = [&]() {
+            if (G16 && part < 0) {   // rounded to bf16: 8 bytes per lane, rows of 256 contiguous bytes
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int idx = lane + 64 * i, key = idx >> 5, q4 = (idx & 31) * 4;
+                    if (key < st_nkeys)
+                        store_grad4(q4 < kD ? a.dK : a.dV, base + (int64_t)(st_node0 + key) * a.sn + (q4 & (kD - 1)),
+                                    *reinterpret_cast<const float4*>(o_s + key * kKvOutStride + q4), true);
+                }
+                return;
+            }
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 const int idx = lane + 64 * i, key = idx >> 5, q4 = (idx & 31) * 4;
@@ -642,8 +664,8 @@ __global__ void __launch_bounds__(256) kv_tile_merge_kernel(const KeyArgs a, con
             if (todo) todo &= todo - 1;
             const int r = lane < 32 ? ra : rb;
             if (r >= 0) {
-                float* dst = ((lane & 16) ? a.dV : a.dK) + base + (int64_t)(first + r) * a.sn + 4 * (lane & 15);
-                store_once(reinterpret_cast<float4*>(dst), make_float4(0.f, 0.f, 0.f, 0.f));
+                store_grad4((lane & 16) ? a.dV : a.dK, base + (int64_t)(first + r) * a.sn + 4 * (lane & 15),
+                            make_float4(0.f, 0.f, 0.f, 0.f), a.grad_bf16);
             }
         }
         return;
@@ -680,8 +702,7 @@ __global__ void __launch_bounds__(256) kv_tile_merge_kernel(const KeyArgs a, con
         }
         const float4 t = make_float4((s0.x + s1.x) + (s2.x + s3.x), (s0.y + s1.y) + (s2.y + s3.y),
                                      (s0.z + s1.z) + (s2.z + s3.z), (s0.w + s1.w) + (s2.w + s3.w));
-        float* dst = (q4 < kD ? a.dK + q4 : a.dV + (q4 - kD)) + base + (int64_t)(node0 + key) * a.sn;
-        store_once(reinterpret_cast<float4*>(dst), t);
+        store_grad4(q4 < kD ? a.dK : a.dV, base + (int64_t)(node0 + key) * a.sn + (q4 & (kD - 1)), t, a.grad_bf16);
     }
 }
 
@@ -699,8 +720,8 @@ __global__ void __launch_bounds__(256) bwd_kv_merge_kernel(const AttnArgs a, con
         sv += src[kD + lane];
     }
     const int64_t at = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh + (int64_t)multi_row[j] * a.sn + lane;
-    a.dK[at] = sk;
-    a.dV[at] = sv;
+    store_grad(a.dK, at, sk, a.grad_bf16);
+    store_grad(a.dV, at, sv, a.grad_bf16);
 }
 
 // d_rel = sum of the workgroups' copies, in a fixed order; rows the copies do not

@@ -36,6 +36,7 @@ struct SpanArgs {
     float scale;
     const int32_t* seq_len;   // [B] tokens of every sequence, or null
     int32_t leave_unkept;     // rows of nodes a shorter sequence does not keep: left unwritten instead of zero-filled
+    int32_t grad_bf16;        // dQ leaves rounded to bf16
     uint32_t drop_thr, drop_seed;   // dropout on the attention weights (DROP variants)
     float drop_inv_keep;
 };
@@ -92,7 +93,7 @@ __device__ __forceinline__ void span_block_gone(const SpanArgs& a, int bh, int t
         } else {
             if (!a.leave_unkept)
                 for (int i = lane; i < cnt * 16; i += 64)    // 64 floats per row
-                    *reinterpret_cast<float4*>(a.dQ + base + (int64_t)(node0 + (i >> 4)) * a.sn + (i & 15) * 4) = make_float4(0.f, 0.f, 0.f, 0.f);
+                    store_grad4(a.dQ, base + (int64_t)(node0 + (i >> 4)) * a.sn + (i & 15) * 4, make_float4(0.f, 0.f, 0.f, 0.f), a.grad_bf16);
             if (lane < cnt) a.stat[(int64_t)bh * a.N + node0 + lane] = make_float2(kLseGone, 0.f);
         }
     }
@@ -362,7 +363,7 @@ __global__ void __launch_bounds__(kSpanBigThreads) fwd_span_merge_kernel(const S
 // and dS = w - delta p are final and dQ = scale * dS K_block (r_anc drops out: the dS of a row
 // sum to zero).  An ancestor stores the partial sums A = W K, Bv = P K, delta, which the merge
 // kernel turns into dQ = scale * (sum A - delta * sum Bv).
-template <bool DROP>
+template <bool DROP, bool G16>   // G16: dQ leaves rounded to bf16
 __global__ void __launch_bounds__(kTileThreads, 3) bwd_q_span_tile_kernel(const SpanArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int lane = threadIdx.x & 63;
@@ -470,13 +471,24 @@ __global__ void __launch_bounds__(kTileThreads, 3) bwd_q_span_tile_kernel(const 
             }
             if (g == 0 && valid)
                 a.stat[(int64_t)bh * a.N + node] = make_float2((((t0 >> level) + loc) << level) < len ? lse2 : kLseGone, dl);
+            if (G16) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int slot = 4 * g + r;
-                if (grp == 1 && slot == 15) continue;
-                float* orow = a.dQ + base + (int64_t)span_slot_node(grp, slot, a.L, a.n, t0) * a.sn + j;
+                for (int r = 0; r < 4; ++r) {
+                    const int slot = 4 * g + r;
+                    if (grp == 1 && slot == 15) continue;
+                    bf16_t* orow = reinterpret_cast<bf16_t*>(a.dQ) + base + (int64_t)span_slot_node(grp, slot, a.L, a.n, t0) * a.sn + j;
 #pragma unroll
-                for (int f = 0; f < 4; ++f) store_once(&orow[16 * f], a.scale * dq[f][r]);
+                    for (int f = 0; f < 4; ++f) store_once(&orow[16 * f], (bf16_t)to_bf16_bits(a.scale * dq[f][r]));
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int slot = 4 * g + r;
+                    if (grp == 1 && slot == 15) continue;
+                    float* orow = a.dQ + base + (int64_t)span_slot_node(grp, slot, a.L, a.n, t0) * a.sn + j;
+#pragma unroll
+                    for (int f = 0; f < 4; ++f) store_once(&orow[16 * f], a.scale * dq[f][r]);
+                }
             }
         } else {
             uint32_t whi[4], wlo[4], phi[4], plo[4];
@@ -542,7 +554,7 @@ __device__ __forceinline__ void bwd_q_span_merge_small(const SpanArgs& a, int it
             dl += xd[b];
         }
     const int64_t base = (int64_t)(r.bh / a.H) * a.sb + (int64_t)(r.bh % a.H) * a.sh;
-    store_once(&a.dQ[base + (int64_t)r.v * a.sn + lane], a.scale * (sa - dl * sb));
+    store_grad(a.dQ, base + (int64_t)r.v * a.sn + lane, a.scale * (sa - dl * sb), a.grad_bf16);
     if (lane == 0) a.stat[(int64_t)r.bh * a.N + r.v] = make_float2(span_row_lse2(a, r), dl);
 }
 
@@ -583,7 +595,7 @@ __global__ void __launch_bounds__(kSpanBigThreads) bwd_q_span_merge_kernel(const
             td += s_d[p];
         }
         const int64_t base = (int64_t)(r.bh / a.H) * a.sb + (int64_t)(r.bh % a.H) * a.sh;
-        store_once(&a.dQ[base + (int64_t)r.v * a.sn + t], a.scale * (ta - td * tb));
+        store_grad(a.dQ, base + (int64_t)r.v * a.sn + t, a.scale * (ta - td * tb), a.grad_bf16);
         if (t == 0) a.stat[(int64_t)r.bh * a.N + r.v] = make_float2(span_row_lse2(a, r), td);
     }
 }

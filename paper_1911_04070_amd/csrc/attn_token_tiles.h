@@ -53,6 +53,7 @@ struct TileArgs {
     // sequences shorter than n
     const int32_t *seq_len, *id_to_cid;
     int32_t leave_unkept;   // rows of nodes a shorter sequence does not keep: left unwritten instead of zero-filled
+    int32_t grad_bf16;      // dQ leaves rounded to bf16
     int32_t n, k, W, ctx_levels, causal;
     // dropout on the attention weights (DROP variants of the kernels)
     uint32_t drop_thr, drop_seed;
@@ -547,12 +548,12 @@ __global__ void __launch_bounds__(kTileThreads, DENSE ? 1 : 2) bwd_q_tile_kernel
     int live_total = 0;
     auto zero_rows = [&](int bh, int tile) {   // dQ of a tile past the end of its sequence; `stat` switches its rows off on the key side
         const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
-        float* qrow = a.dQ + base + (int64_t)(tile * 16 + r8) * a.sn + piece * 8;
+        const int64_t qrow = base + (int64_t)(tile * 16 + r8) * a.sn + piece * 8;
         if (!a.leave_unkept) {
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                *reinterpret_cast<float4*>(qrow + (int64_t)8 * h * a.sn) = make_float4(0.f, 0.f, 0.f, 0.f);
-                *reinterpret_cast<float4*>(qrow + (int64_t)8 * h * a.sn + 4) = make_float4(0.f, 0.f, 0.f, 0.f);
+                store_grad4(a.dQ, qrow + (int64_t)8 * h * a.sn, make_float4(0.f, 0.f, 0.f, 0.f), a.grad_bf16);
+                store_grad4(a.dQ, qrow + (int64_t)8 * h * a.sn + 4, make_float4(0.f, 0.f, 0.f, 0.f), a.grad_bf16);
             }
         }
         if (lane < 16) a.stat[(int64_t)bh * a.N + tile * 16 + lane] = make_float2(kLseGone, 0.f);
@@ -900,13 +901,25 @@ __global__ void __launch_bounds__(kTileThreads, DENSE ? 1 : 2) bwd_q_tile_kernel
                     }
                 wave_lds_sync();   // before the next tile clears the tables and forms its bias table
             }
-            float* qrow_out = a.dQ + base + (int64_t)t0 * a.sn + j;
+            const int64_t qrow_out = base + (int64_t)t0 * a.sn + j;
+            float dr[4];
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const float dr = __shfl(delta, 4 * g + r);
+            for (int r = 0; r < 4; ++r) dr[r] = __shfl(delta, 4 * g + r);
+            if (a.grad_bf16) {   // one branch around all stores of the tile
+                bf16_t* dst = reinterpret_cast<bf16_t*>(a.dQ) + qrow_out;
 #pragma unroll
-                for (int f = 0; f < 4; ++f)
-                    store_once(&qrow_out[(int64_t)(4 * g + r) * a.sn + 16 * f], a.scale * (ow[f][r] - dr * op[f][r] + dqr[f][r]));
+                for (int r = 0; r < 4; ++r)
+#pragma unroll
+                    for (int f = 0; f < 4; ++f)
+                        store_once(&dst[(int64_t)(4 * g + r) * a.sn + 16 * f],
+                                   (bf16_t)to_bf16_bits(a.scale * (ow[f][r] - dr[r] * op[f][r] + dqr[f][r])));
+            } else {
+                float* dst = a.dQ + qrow_out;
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+#pragma unroll
+                    for (int f = 0; f < 4; ++f)
+                        store_once(&dst[(int64_t)(4 * g + r) * a.sn + 16 * f], a.scale * (ow[f][r] - dr[r] * op[f][r] + dqr[f][r]));
             }
         }
         cc = cr;
@@ -938,6 +951,7 @@ struct RelGradArgs {
     int32_t BH, H, N, n, num_tiles, num_chunks, num_cids, nids;   // nids = ids padded to 32
     float scale;
     const int32_t* seq_len;   // [B] tokens of every sequence, or null
+    int32_t grad_bf16;        // dQ holds bf16 elements
 };
 // tile slots per thread fetched one block ahead: 8 (512 threads: 16 chunks) with up to 256 ids, 24 with more --
 // those graphs have 25..30 slots per thread and block, and one workgroup per compute unit to hide their latency
@@ -1063,7 +1077,7 @@ __global__ void __launch_bounds__(kThreads, CPW == 2 ? 4 : 2) rel_grad_tile_kern
 #pragma unroll
         for (int m = 0; m < 4; ++m) {
             const int row = row0 + 16 * mc + 4 * g + m;
-            dq_old[m] = row < a.n ? a.dQ[base + (int64_t)row * a.sn + 16 * fc + j] : 0.f;
+            dq_old[m] = row < a.n ? load_grad(a.dQ, base + (int64_t)row * a.sn + 16 * fc + j, a.grad_bf16) : 0.f;
         }
         const int blk_next = next_block(blk + gridDim.x);
         if (blk_next < total) prefetch(blk_next);
@@ -1078,7 +1092,7 @@ __global__ void __launch_bounds__(kThreads, CPW == 2 ? 4 : 2) rel_grad_tile_kern
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
                 const int row = row0 + 16 * mc + 4 * g + m;
-                if (row < a.n) store_once(&a.dQ[base + (int64_t)row * a.sn + 16 * fc + j], dq_old[m] + a.scale * dq[m]);
+                if (row < a.n) store_grad(a.dQ, base + (int64_t)row * a.sn + 16 * fc + j, dq_old[m] + a.scale * dq[m], a.grad_bf16);
             }
         }
         bf16x8_t qb[4];

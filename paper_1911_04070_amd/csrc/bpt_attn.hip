@@ -74,6 +74,8 @@ int check_shape(const bpt_graph* g, const bpt_shape_t* s) {
     if (s->stride_n < kD || (s->stride_n % 8) || (s->stride_h % 8) || (s->stride_b % 8)) return BPT_ERR_INVALID_ARG;
     if (s->stride_h < 0 || s->stride_b < 0) return BPT_ERR_INVALID_ARG;
     if (!(s->dropout_p >= 0.f && s->dropout_p < 1.f)) return BPT_ERR_INVALID_ARG;
+    // gradients rounded to bf16 are for bf16 tensors
+    if (s->grad_dtype != BPT_F32 && !(s->grad_dtype == BPT_BF16 && s->dtype == BPT_BF16)) return BPT_ERR_INVALID_ARG;
     // a batch graph carries the lengths itself; dropout masks are defined on the nodes of one tree
     if (g->batch > 0 && s->seq_len) return BPT_ERR_INVALID_ARG;
     if (g->batch > 0 && s->dropout_p > 0.f) return BPT_ERR_UNSUPPORTED;
@@ -153,6 +155,7 @@ void fill_common(AttnArgs& a, const bpt_graph* g, const bpt_shape_t* s) {
     a.idx_bytes = (uint32_t)(g->num_edges * 4);
     a.seq_len = s->seq_len;
     a.leave_unkept = s->seq_len && s->leave_unkept ? 1 : 0;
+    a.grad_bf16 = s->grad_dtype == BPT_BF16 ? 1 : 0;
     a.lg = g->num_levels - 1;
     const double p = s->dropout_p > 0.f ? (double)s->dropout_p : 0.0;
     a.drop_thr = p > 0.0 ? (uint32_t)std::min(std::floor(p * 4294967296.0), 4294967295.0) : 0u;
@@ -265,6 +268,7 @@ void fill_tile_args(TileArgs& t, const bpt_graph* g, const AttnArgs& a, const Ti
     t.slab_bytes = a.slab_bytes;
     t.seq_len = a.seq_len;
     t.leave_unkept = a.leave_unkept;
+    t.grad_bf16 = a.grad_bf16;
     t.id_to_cid = g->tiles.id_to_cid;
     t.n = g->n;
     t.k = g->k;
@@ -313,6 +317,7 @@ void fill_span_args(SpanArgs& t, const bpt_graph* g, const AttnArgs& a) {
     t.scale = a.scale;
     t.seq_len = a.seq_len;
     t.leave_unkept = a.leave_unkept;
+    t.grad_bf16 = a.grad_bf16;
     t.drop_thr = a.drop_thr;
     t.drop_seed = a.drop_seed;
     t.drop_inv_keep = a.drop_inv_keep;
@@ -328,10 +333,14 @@ int run_span_tiles(const bpt_graph* g, const AttnArgs& a, bool forward, hipStrea
         BPT_LAUNCH("fwd_span_tile_kernel", fwd_span_tile_kernel<true>, dim3(grid), dim3(kTileThreads), lds, st, t);
     else if (forward)
         BPT_LAUNCH("fwd_span_tile_kernel", fwd_span_tile_kernel<false>, dim3(grid), dim3(kTileThreads), lds, st, t);
+    else if (t.drop_thr && t.grad_bf16)
+        BPT_LAUNCH("bwd_q_span_tile_kernel", (bwd_q_span_tile_kernel<true, true>), dim3(grid), dim3(kTileThreads), lds, st, t);
     else if (t.drop_thr)
-        BPT_LAUNCH("bwd_q_span_tile_kernel", bwd_q_span_tile_kernel<true>, dim3(grid), dim3(kTileThreads), lds, st, t);
+        BPT_LAUNCH("bwd_q_span_tile_kernel", (bwd_q_span_tile_kernel<true, false>), dim3(grid), dim3(kTileThreads), lds, st, t);
+    else if (t.grad_bf16)
+        BPT_LAUNCH("bwd_q_span_tile_kernel", (bwd_q_span_tile_kernel<false, true>), dim3(grid), dim3(kTileThreads), lds, st, t);
     else
-        BPT_LAUNCH("bwd_q_span_tile_kernel", bwd_q_span_tile_kernel<false>, dim3(grid), dim3(kTileThreads), lds, st, t);
+        BPT_LAUNCH("bwd_q_span_tile_kernel", (bwd_q_span_tile_kernel<false, false>), dim3(grid), dim3(kTileThreads), lds, st, t);
     BPT_HIP(hipGetLastError());
     if (t.L > kSpanInLevels) {
         // rows of levels 6..9 (at most 16 partials each), then the longer rows
@@ -564,6 +573,7 @@ int run_bwd_q(const bpt_graph* g, const BwdPlan& p, AttnArgs& a, hipStream_t st)
         t.nids = p.drel_part_rows;
         t.scale = a.scale;
         t.seq_len = a.seq_len;
+        t.grad_bf16 = a.grad_bf16;
         if (p.dense_ds) {
             // bwd_q_tile_kernel has left the copies of d_rel
         } else if (p.drel_part_rows <= 256) {
@@ -613,20 +623,22 @@ template <int NBC>
 int launch_kv_tiles(const KeyArgs& t, const BwdPlan& p, const DeviceLimits& lim, hipStream_t st) {
     return t.drop_thr ? launch_kv_tiles_as<NBC, true>(t, p, lim, st) : launch_kv_tiles_as<NBC, false>(t, p, lim, st);
 }
-template <int NBC, bool DROP>
+template <int NBC, bool DROP, bool G16>
 int launch_kv_chain_as(const KeyArgs& t, const BwdPlan& p, const DeviceLimits& lim, hipStream_t st) {
     if (p.kv_lds > 65536)
-        BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_kv_chain_kernel<NBC, DROP>),
+        BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_kv_chain_kernel<NBC, DROP, G16>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.kv_lds));
     const int grid =
-        std::max(8, lim.cus * resident_blocks(bwd_kv_chain_kernel<NBC, DROP>, kTileThreads, p.kv_lds, lim) / 8 * 8);
-    BPT_LAUNCH("bwd_kv_chain_kernel", (bwd_kv_chain_kernel<NBC, DROP>), dim3(grid), dim3(kTileThreads), p.kv_lds, st, t);
+        std::max(8, lim.cus * resident_blocks(bwd_kv_chain_kernel<NBC, DROP, G16>, kTileThreads, p.kv_lds, lim) / 8 * 8);
+    BPT_LAUNCH("bwd_kv_chain_kernel", (bwd_kv_chain_kernel<NBC, DROP, G16>), dim3(grid), dim3(kTileThreads), p.kv_lds, st, t);
     BPT_HIP(hipGetLastError());
     return BPT_OK;
 }
 template <int NBC>
 int launch_kv_chain(const KeyArgs& t, const BwdPlan& p, const DeviceLimits& lim, hipStream_t st) {
-    return t.drop_thr ? launch_kv_chain_as<NBC, true>(t, p, lim, st) : launch_kv_chain_as<NBC, false>(t, p, lim, st);
+    if (t.grad_bf16)
+        return t.drop_thr ? launch_kv_chain_as<NBC, true, true>(t, p, lim, st) : launch_kv_chain_as<NBC, false, true>(t, p, lim, st);
+    return t.drop_thr ? launch_kv_chain_as<NBC, true, false>(t, p, lim, st) : launch_kv_chain_as<NBC, false, false>(t, p, lim, st);
 }
 
 // bf16 key side on dense tiles of key nodes
@@ -672,6 +684,7 @@ int run_bwd_kv_tiles(const bpt_graph* g, const BwdPlan& p, const AttnArgs& a, co
     t.num_chunks = kt.num_chunks;
     t.seq_len = a.seq_len;
     t.leave_unkept = a.leave_unkept;
+    t.grad_bf16 = a.grad_bf16;
     t.n = g->n;
     t.drop_thr = a.drop_thr;
     t.drop_seed = a.drop_seed;
@@ -744,7 +757,7 @@ int run_bwd_kv(const bpt_graph* g, const BwdPlan& p, AttnArgs& a, bool queue_cle
 enum { kStageQ = 1, kStageKV = 2 };
 
 int backward(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q, const void* K, const void* V, const void* rel,
-             const float* lse, const void* dout, float* dQ, float* dK, float* dV, float* d_rel, void* workspace,
+             const float* lse, const void* dout, void* dQ, void* dK, void* dV, float* d_rel, void* workspace,
              size_t workspace_bytes, void* stream, int stages) {
     int rc = check_shape(g, s);
     if (rc) return rc;
@@ -766,9 +779,9 @@ int backward(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q, const vo
     a.rel = rel;
     a.lse_r = lse;
     a.dout = dout;
-    a.dQ = dQ;
-    a.dK = dK;
-    a.dV = dV;
+    a.dQ = static_cast<float*>(dQ);   // bf16 elements with grad_dtype = BPT_BF16 (AttnArgs.grad_bf16)
+    a.dK = static_cast<float*>(dK);
+    a.dV = static_cast<float*>(dV);
     a.d_rel = d_rel;
     a.stat = reinterpret_cast<float2*>(ws + p.off_stat);
     a.wp = reinterpret_cast<float2*>(ws + p.off_wp);
@@ -853,21 +866,21 @@ int bpt_attn_fwd_static(const bpt_graph_t* g, const bpt_shape_t* s, const void* 
 }
 
 int bpt_attn_bwd(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q, const void* K, const void* V,
-                 const void* rel, const float* lse, const void* dout, float* dQ, float* dK, float* dV, float* d_rel,
+                 const void* rel, const float* lse, const void* dout, void* dQ, void* dK, void* dV, float* d_rel,
                  void* workspace, size_t workspace_bytes, void* stream) {
     return bpt::backward(g, s, Q, K, V, rel, lse, dout, dQ, dK, dV, d_rel, workspace, workspace_bytes, stream,
                          bpt::kStageQ | bpt::kStageKV);
 }
 
 int bpt_attn_bwd_query_side(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q, const void* K, const void* V,
-                            const void* rel, const float* lse, const void* dout, float* dQ, float* d_rel,
+                            const void* rel, const float* lse, const void* dout, void* dQ, float* d_rel,
                             void* workspace, size_t workspace_bytes, void* stream) {
     return bpt::backward(g, s, Q, K, V, rel, lse, dout, dQ, nullptr, nullptr, d_rel, workspace, workspace_bytes,
                          stream, bpt::kStageQ);
 }
 
 int bpt_attn_bwd_key_side(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q, const void* K, const void* V,
-                          const void* rel, const float* lse, const void* dout, float* dK, float* dV, void* workspace,
+                          const void* rel, const float* lse, const void* dout, void* dK, void* dV, void* workspace,
                           size_t workspace_bytes, void* stream) {
     return bpt::backward(g, s, Q, K, V, rel, lse, dout, nullptr, dK, dV, nullptr, workspace, workspace_bytes, stream,
                          bpt::kStageKV);

@@ -325,22 +325,19 @@ __global__ void __launch_bounds__(256) sum_slices_kernel(const float* __restrict
     *reinterpret_cast<float4*>(o.out[col / o.cols_each] + row * o.cols_each + col % o.cols_each) = acc;
 }
 
-// dst (bf16) [rows][3 d] = src0 | src1 | src2 (fp32, [rows][d] each) side by side, 8 values per thread;
-// blockIdx.y picks the tensor
-struct CastArgs {
-    const float* src[3];
+// dst (bf16) [d][3 d] = Wq | Wk | Wv ([d][d] each) side by side, 8 values per thread; blockIdx.y picks the matrix.
+// One projection X [Wq | Wk | Wv] then reads X once and gives the three results side by side.
+struct PackArgs {
+    const bf16_t* src[3];
     bf16_t* dst;
 };
-__global__ void __launch_bounds__(256) cast_bf16_kernel(const CastArgs t, int64_t chunks, int d) {
+__global__ void __launch_bounds__(256) pack_qkv_weights_kernel(const PackArgs t, int64_t chunks, int d) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= chunks) return;
-    const float* src = t.src[blockIdx.y] + i * 8;
-    const float4 a = *reinterpret_cast<const float4*>(src), b = *reinterpret_cast<const float4*>(src + 4);
     const int64_t row = (i * 8) / d;
     const int col = (int)(i * 8 - row * d);
     *reinterpret_cast<uint4*>(t.dst + row * 3 * d + (int64_t)blockIdx.y * d + col) =
-        make_uint4(f32_to_bf16(a.x) | (f32_to_bf16(a.y) << 16), f32_to_bf16(a.z) | (f32_to_bf16(a.w) << 16),
-                   f32_to_bf16(b.x) | (f32_to_bf16(b.y) << 16), f32_to_bf16(b.z) | (f32_to_bf16(b.w) << 16));
+        *reinterpret_cast<const uint4*>(t.src[blockIdx.y] + i * 8);
 }
 
 // y (bf16) = x (bf16) + a (fp32), 8 values per thread
@@ -418,13 +415,14 @@ rocblas_handle blas_handle(int device) {
 // with tb.  rocBLAS is column-major: C^T = op(B)^T op(A)^T with the same buffers, a row-major
 // [r][c] buffer being the column-major c x r matrix with leading dimension c.
 int gemm_rm(rocblas_handle h, int64_t M, int64_t N, int64_t K, const void* A, bool ta, const void* B, bool tb, void* C,
-            bool c_fp32, float beta = 0.f, int64_t lda = 0) {   // lda: elements between rows of A as stored (0: dense)
+            bool c_fp32, float beta = 0.f, int64_t lda = 0, int64_t ldc = 0) {   // lda, ldc: elements between rows of A, C as stored (0: dense)
     const float one = 1.f;
     const rocblas_datatype ct = c_fp32 ? rocblas_datatype_f32_r : rocblas_datatype_bf16_r;
+    const rocblas_int ldc_ = (rocblas_int)(ldc ? ldc : N);
     const rocblas_status st = rocblas_gemm_ex(
         h, tb ? rocblas_operation_transpose : rocblas_operation_none, ta ? rocblas_operation_transpose : rocblas_operation_none,
         (rocblas_int)N, (rocblas_int)M, (rocblas_int)K, &one, B, rocblas_datatype_bf16_r, (rocblas_int)(tb ? K : N), A,
-        rocblas_datatype_bf16_r, (rocblas_int)(lda ? lda : (ta ? M : K)), &beta, C, ct, (rocblas_int)N, C, ct, (rocblas_int)N,
+        rocblas_datatype_bf16_r, (rocblas_int)(lda ? lda : (ta ? M : K)), &beta, C, ct, ldc_, C, ct, ldc_,
         rocblas_datatype_f32_r, rocblas_gemm_algo_standard, 0, 0);
     return st == rocblas_status_success ? BPT_OK : BPT_ERR_LAUNCH;
 }
@@ -442,7 +440,7 @@ bool any_misaligned(P... p) {
 }
 
 struct LayerBuffers {
-    size_t q, k, v, o, lse, acc1, acc2, st1, st2, z, f1, attn, total;
+    size_t qkvo, wqkv, lse, acc1, acc2, st1, st2, z, f1, attn, total;
 };
 LayerBuffers layer_buffers(const bpt_graph* g, int B, int H, int d_ff, size_t attn_ws) {
     const size_t rows = (size_t)B * g->num_nodes, d = (size_t)H * kD;
@@ -453,10 +451,8 @@ LayerBuffers layer_buffers(const bpt_graph* g, int B, int H, int d_ff, size_t at
         off += align_up(bytes);
         return at;
     };
-    L.q = take(rows * d * 2);
-    L.k = take(rows * d * 2);
-    L.v = take(rows * d * 2);
-    L.o = take(rows * d * 2);
+    L.qkvo = take(rows * 4 * d * 2);   // [rows][Q | K | V | O]: the projections side by side, then the attention's output
+    L.wqkv = take(d * 3 * d * 2);      // [d][Wq | Wk | Wv]
     L.lse = take((size_t)B * H * g->num_nodes * 4);
     L.acc1 = take(rows * d * 4);     // W^O result, fp32
     L.acc2 = take(rows * d * 4);     // W_2 result, fp32
@@ -475,9 +471,12 @@ bpt_shape_t attn_shape(const bpt_graph* g, int B, int H, float scale, const int3
     s.H = H;
     s.D = kD;
     s.dtype = BPT_BF16;
-    s.stride_n = (int64_t)H * kD;              // [B][N][H][64]: the heads of a node are adjacent
+    // Q, K, V and the attention's output of a node sit side by side, [B][N][Q | K | V | O][H][64] (one projection
+    // writes the first three); the gradients of the backward use the same layout with dO in the fourth place
+    s.stride_n = (int64_t)4 * H * kD;
     s.stride_h = kD;
-    s.stride_b = (int64_t)g->num_nodes * H * kD;
+    s.stride_b = (int64_t)g->num_nodes * 4 * H * kD;
+    s.grad_dtype = BPT_BF16;                   // dQ, dK, dV feed bf16 GEMMs
     s.scale = scale;
     s.seq_len = seq_len;
     return s;
@@ -493,7 +492,7 @@ int pick_slices(int M, int N, int64_t K) {
 constexpr int kColumnSumBlocks = 2048;   // workgroups (= partial rows) of the kernels that sum over rows
 
 struct LayerBwdBuffers {
-    size_t ds2, dh, t, ds1, da, dq, dk, dv, dqkv, part, gw, attn, total;
+    size_t ds2, dh, t, ds1, dqkvo, part, gw, attn, total;
 };
 LayerBwdBuffers layer_bwd_buffers(const bpt_graph* g, int B, int H, int d_ff, size_t attn_ws) {
     const size_t rows = (size_t)B * g->num_nodes, d = (size_t)H * kD;
@@ -508,11 +507,8 @@ LayerBwdBuffers layer_bwd_buffers(const bpt_graph* g, int B, int H, int d_ff, si
     L.dh = take(rows * (size_t)d_ff * 2);    // gradient of the hidden FFN activations, bf16
     L.t = take(rows * d * 4);                // fp32 GEMM results: dH W1^T, later dQ Wq^T + dK Wk^T + dV Wv^T
     L.ds1 = take(rows * d * 2);
-    L.da = take(rows * d * 2);               // gradient of the attention output, [B][N][H][64] bf16
-    L.dq = take(rows * d * 4);               // the attention's fp32 gradients ...
-    L.dk = take(rows * d * 4);
-    L.dv = take(rows * d * 4);
-    L.dqkv = take(rows * 3 * d * 2);         // ... and their bf16 copies side by side, [rows][3 d], for the projections
+    L.dqkvo = take(rows * 4 * d * 2);        // [rows][dQ | dK | dV | dO] bf16: the attention's gradients, rounded to bf16 by its
+                                             // backward, next to the gradient of its output -- the forward's layout
     L.part = take((size_t)kColumnSumBlocks * std::max<size_t>(3 * d, (size_t)d_ff) * 4);
     // partial products of the weight gradients (contraction over the rows, cut into slices)
     const size_t gw_qkv = (size_t)pick_slices((int)d, (int)(3 * d), (int64_t)rows) * d * 3 * d;
@@ -558,21 +554,22 @@ int column_sum(const float* partials, int parts, int cols, int cols_each, float*
 // are added in slice order by sum_slices_kernel.  The N columns are N / n_each matrices side by
 // side that go to out0..out2 (each [M][n_each]).
 int gemm_at_b_sliced(rocblas_handle h, int M, int N, int64_t K, const void* A, const void* B, int ldb_cols, float* partials,
-                     int slices, int n_each, float* out0, float* out1, float* out2, hipStream_t st) {
+                     int slices, int n_each, float* out0, float* out1, float* out2, hipStream_t st, int lda_cols = 0) {
     const float one = 1.f, zero = 0.f;
+    const int lda = lda_cols ? lda_cols : M;   // elements between rows of A as stored
     const int64_t ks = K / slices;
     if (ks < 1) return BPT_ERR_INVALID_ARG;
     // column-major view: C^T (N x M) = B^T-as-stored (N x K, ld = ldb_cols) times A (K x M) given as its transpose
     rocblas_status rs = rocblas_gemm_strided_batched_ex(
         h, rocblas_operation_none, rocblas_operation_transpose, N, M, (rocblas_int)ks, &one, B, rocblas_datatype_bf16_r, ldb_cols,
-        ks * ldb_cols, A, rocblas_datatype_bf16_r, M, ks * (int64_t)M, &zero, partials, rocblas_datatype_f32_r, N, (int64_t)M * N,
+        ks * ldb_cols, A, rocblas_datatype_bf16_r, lda, ks * (int64_t)lda, &zero, partials, rocblas_datatype_f32_r, N, (int64_t)M * N,
         partials, rocblas_datatype_f32_r, N, (int64_t)M * N, slices, rocblas_datatype_f32_r, rocblas_gemm_algo_standard, 0, 0);
     if (rs != rocblas_status_success) return BPT_ERR_LAUNCH;
     const int64_t done = ks * slices;
     if (done < K) {
         rs = rocblas_gemm_ex(h, rocblas_operation_none, rocblas_operation_transpose, N, M, (rocblas_int)(K - done), &one,
                              static_cast<const bf16_t*>(B) + done * ldb_cols, rocblas_datatype_bf16_r, ldb_cols,
-                             static_cast<const bf16_t*>(A) + done * M, rocblas_datatype_bf16_r, M, &one, partials,
+                             static_cast<const bf16_t*>(A) + done * lda, rocblas_datatype_bf16_r, lda, &one, partials,
                              rocblas_datatype_f32_r, N, partials, rocblas_datatype_f32_r, N, rocblas_datatype_f32_r,
                              rocblas_gemm_algo_standard, 0, 0);
         if (rs != rocblas_status_success) return BPT_ERR_LAUNCH;
@@ -636,7 +633,9 @@ int bpt_layer_fwd(const bpt_graph_t* g, int32_t B, int32_t H, float scale, const
     rocblas_handle h = blas_handle(g->device);
     if (!h || rocblas_set_stream(h, st) != rocblas_status_success) return BPT_ERR_LAUNCH;
     unsigned char* ws = static_cast<unsigned char*>(workspace);
-    void *q = ws + L.q, *k = ws + L.k, *v = ws + L.v, *o = ws + L.o, *z = ws + L.z, *f1 = ws + L.f1;
+    bf16_t* qkvo = reinterpret_cast<bf16_t*>(ws + L.qkvo);
+    bf16_t* wqkv = reinterpret_cast<bf16_t*>(ws + L.wqkv);
+    void *q = qkvo, *k = qkvo + d, *v = qkvo + 2 * d, *o = qkvo + 3 * d, *z = ws + L.z, *f1 = ws + L.f1;
     float* lse = reinterpret_cast<float*>(ws + L.lse);
     float* acc1 = reinterpret_cast<float*>(ws + L.acc1);
     float* acc2 = reinterpret_cast<float*>(ws + L.acc2);
@@ -644,13 +643,18 @@ int bpt_layer_fwd(const bpt_graph_t* g, int32_t B, int32_t H, float scale, const
     float2* st2 = reinterpret_cast<float2*>(ws + L.st2);
     const float eps = p->eps > 0.f ? p->eps : 1e-5f;
     int rc;
-    // Q, K, V = X Wq, X Wk, X Wv for all nodes: [B][N][H][64], the layout the attention reads through its strides
-    if ((rc = gemm_rm(h, rows, d, d, X, p->Wq, q, false)) || (rc = gemm_rm(h, rows, d, d, X, p->Wk, k, false)) ||
-        (rc = gemm_rm(h, rows, d, d, X, p->Wv, v, false)))
-        return rc;
+    // [Q | K | V] = X [Wq | Wk | Wv] for all nodes in one product that reads X once: rows of [Q | K | V | O][H][64],
+    // the layout the attention reads and writes through its strides (the packed weights stay in the workspace for
+    // the backward)
+    const PackArgs pa = {{static_cast<const bf16_t*>(p->Wq), static_cast<const bf16_t*>(p->Wk), static_cast<const bf16_t*>(p->Wv)}, wqkv};
+    const int64_t wchunks = (int64_t)d * d / 8;
+    BPT_LAUNCH("pack_qkv_weights_kernel", pack_qkv_weights_kernel, dim3((unsigned)((wchunks + 255) / 256), 3), dim3(256), 0, st, pa,
+               wchunks, d);
+    BPT_HIP(hipGetLastError());
+    if ((rc = gemm_rm(h, rows, 3 * d, d, X, false, wqkv, false, qkvo, false, 0.f, 0, 4 * d))) return rc;
     if ((rc = bpt_attn_fwd(g, &s, q, k, v, rel, o, lse, ws + L.attn, attn_ws, stream))) return rc;
     // Z = norm(X + O Wo)
-    if ((rc = gemm_rm(h, rows, d, d, o, p->Wo, acc1, true))) return rc;
+    if ((rc = gemm_rm(h, rows, d, d, o, false, p->Wo, false, acc1, true, 0.f, 4 * d))) return rc;
     const unsigned ln_blocks = (unsigned)((rows + 3) / 4);
     BPT_LAUNCH("residual_layer_norm_kernel", residual_layer_norm_kernel, dim3(ln_blocks), dim3(256), 0, st,
                static_cast<const bf16_t*>(X), acc1, static_cast<const float*>(nullptr), p->g1, p->beta1, static_cast<bf16_t*>(z),
@@ -708,17 +712,18 @@ int bpt_layer_bwd(const bpt_graph_t* g, int32_t B, int32_t H, float scale, const
     if (!h || rocblas_set_stream(h, st) != rocblas_status_success) return BPT_ERR_LAUNCH;
     const unsigned char* fw = static_cast<const unsigned char*>(fwd_workspace);
     unsigned char* ws = static_cast<unsigned char*>(workspace);
-    const void *q = fw + F.q, *k = fw + F.k, *v = fw + F.v, *o = fw + F.o;
+    const bf16_t* qkvo = reinterpret_cast<const bf16_t*>(fw + F.qkvo);
+    const bf16_t* wqkv = reinterpret_cast<const bf16_t*>(fw + F.wqkv);
+    const void *q = qkvo, *k = qkvo + d, *v = qkvo + 2 * d, *o = qkvo + 3 * d;
     const bf16_t* z = reinterpret_cast<const bf16_t*>(fw + F.z);
     const bf16_t* f1 = reinterpret_cast<const bf16_t*>(fw + F.f1);
     const float* lse = reinterpret_cast<const float*>(fw + F.lse);
     const float *acc1 = reinterpret_cast<const float*>(fw + F.acc1), *acc2 = reinterpret_cast<const float*>(fw + F.acc2);
     const float2 *st1 = reinterpret_cast<const float2*>(fw + F.st1), *st2 = reinterpret_cast<const float2*>(fw + F.st2);
     bf16_t *ds2 = reinterpret_cast<bf16_t*>(ws + L.ds2), *dh = reinterpret_cast<bf16_t*>(ws + L.dh);
-    bf16_t *ds1 = reinterpret_cast<bf16_t*>(ws + L.ds1), *da = reinterpret_cast<bf16_t*>(ws + L.da);
+    bf16_t *ds1 = reinterpret_cast<bf16_t*>(ws + L.ds1), *dqkvo = reinterpret_cast<bf16_t*>(ws + L.dqkvo);
+    bf16_t* da = dqkvo + 3 * d;
     float *t = reinterpret_cast<float*>(ws + L.t), *part = reinterpret_cast<float*>(ws + L.part);
-    float *dq = reinterpret_cast<float*>(ws + L.dq), *dk = reinterpret_cast<float*>(ws + L.dk), *dv = reinterpret_cast<float*>(ws + L.dv);
-    bf16_t* dqkv = reinterpret_cast<bf16_t*>(ws + L.dqkv);
     float* gw = reinterpret_cast<float*>(ws + L.gw);
     const int lg = 31 - __builtin_clz((unsigned)g->n);
     const int ln_blocks = (int)std::min<int64_t>(kColumnSumBlocks, (rows + 3) / 4);
@@ -749,21 +754,18 @@ int bpt_layer_bwd(const bpt_graph_t* g, int32_t B, int32_t H, float scale, const
         return rc;
     if ((rc = column_sum(part, ln_blocks, 3 * d, d, gr->dg1, gr->dbeta1, nullptr, st))) return rc;
     // attention sublayer: dWo = O^T dS1, dO = dS1 Wo^T, then the attention's own backward
-    if ((rc = gemm_at_b_sliced(h, d, d, rows, o, ds1, d, gw, pick_slices(d, d, rows), d, gr->dWo, nullptr, nullptr, st))) return rc;
-    if ((rc = gemm_rm(h, rows, d, d, ds1, false, p->Wo, true, da, false))) return rc;
-    if ((rc = bpt_attn_bwd(g, &s, q, k, v, rel, lse, da, dq, dk, dv, d_rel, ws + L.attn, attn_ws, stream))) return rc;
-    const CastArgs ca = {{dq, dk, dv}, dqkv};
+    if ((rc = gemm_at_b_sliced(h, d, d, rows, o, ds1, d, gw, pick_slices(d, d, rows), d, gr->dWo, nullptr, nullptr, st, 4 * d)))
+        return rc;
+    if ((rc = gemm_rm(h, rows, d, d, ds1, false, p->Wo, true, da, false, 0.f, 0, 4 * d))) return rc;
+    // dQ, dK, dV leave the attention's backward rounded to bf16, side by side next to dO: no cast pass
+    if ((rc = bpt_attn_bwd(g, &s, q, k, v, rel, lse, da, dqkvo, dqkvo + d, dqkvo + 2 * d, d_rel, ws + L.attn, attn_ws, stream)))
+        return rc;
     const int64_t chunks = rows * d / 8;
-    BPT_LAUNCH("cast_bf16_kernel", cast_bf16_kernel, dim3((unsigned)((chunks + 255) / 256), 3), dim3(256), 0, st, ca, chunks, d);
-    BPT_HIP(hipGetLastError());
-    // projections: [dWq | dWk | dWv] = X^T [dQ | dK | dV] in one product, dX = dS1 + dQ Wq^T + dK Wk^T + dV Wv^T
-    if ((rc = gemm_at_b_sliced(h, d, 3 * d, rows, X, dqkv, 3 * d, gw, pick_slices(d, 3 * d, rows), d, gr->dWq, gr->dWk, gr->dWv,
+    // projections, one product each: [dWq | dWk | dWv] = X^T [dQ | dK | dV], dX = dS1 + [dQ | dK | dV] [Wq | Wk | Wv]^T
+    if ((rc = gemm_at_b_sliced(h, d, 3 * d, rows, X, dqkvo, 4 * d, gw, pick_slices(d, 3 * d, rows), d, gr->dWq, gr->dWk, gr->dWv,
                                st)))
         return rc;
-    if ((rc = gemm_rm(h, rows, d, d, dqkv, false, p->Wq, true, t, true, 0.f, 3 * d)) ||
-        (rc = gemm_rm(h, rows, d, d, dqkv + d, false, p->Wk, true, t, true, 1.f, 3 * d)) ||
-        (rc = gemm_rm(h, rows, d, d, dqkv + 2 * d, false, p->Wv, true, t, true, 1.f, 3 * d)))
-        return rc;
+    if ((rc = gemm_rm(h, rows, d, 3 * d, dqkvo, false, wqkv, true, t, true, 0.f, 4 * d))) return rc;
     BPT_LAUNCH("add_cast_kernel", add_cast_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st,
                static_cast<const bf16_t*>(ds1), static_cast<const float*>(t), static_cast<bf16_t*>(dX), chunks);
     BPT_HIP(hipGetLastError());

@@ -53,10 +53,25 @@ def test_build_graph_rejects_bad_sizes_on_the_host(n, k, code):
     assert lib.bpt_build_graph(8, 2, 0, None, None) == bpt.BPT_ERR_INVALID_ARG
 
 
+def test_build_batch_graph_rejects_bad_arguments_on_the_host():
+    lib = bpt.load_library()
+    lens = (ctypes.c_int32 * 3)(4, 65, 2)
+    for args, code in (((64, 2, 0, lens, 3), bpt.BPT_ERR_INVALID_ARG),          # a length above n
+                       ((64, 2, 0, None, 3), bpt.BPT_ERR_INVALID_ARG), ((64, 2, 0, lens, 0), bpt.BPT_ERR_INVALID_ARG),
+                       ((48, 2, 0, lens, 1), bpt.BPT_ERR_UNSUPPORTED), ((64, 0, 0, lens, 1), bpt.BPT_ERR_INVALID_ARG),
+                       ((64, 2, 0, lens, (1 << 16) + 1), bpt.BPT_ERR_UNSUPPORTED)):
+        h = ctypes.c_void_p(123)
+        n, k, causal, lengths, batch = args
+        assert lib.bpt_build_batch_graph(n, k, causal, lengths, batch, None, ctypes.byref(h)) == code, args
+        assert h.value is None
+    assert lib.bpt_build_batch_graph(64, 2, 0, lens, 1, None, None) == bpt.BPT_ERR_INVALID_ARG
+
+
 def test_null_graph_is_an_error_everywhere():
     lib = bpt.load_library()
     shp = bpt.BptShape(1, 1, 64, bpt.BPT_F32, 64, 64, 64, 0.0)
     assert lib.bpt_graph_info(None, *([None] * 8)) == bpt.BPT_ERR_INVALID_ARG
+    assert lib.bpt_graph_layout(None, None, None, None, None) == bpt.BPT_ERR_INVALID_ARG
     assert lib.bpt_graph_csr(None, None, None, None) == bpt.BPT_ERR_INVALID_ARG
     assert lib.bpt_graph_transposed(None, None, None, None) == bpt.BPT_ERR_INVALID_ARG
     assert lib.bpt_graph_to_host(None, None, None, None) == bpt.BPT_ERR_INVALID_ARG
@@ -81,10 +96,10 @@ def test_null_graph_is_an_error_everywhere():
 
 def test_shape_struct_layout_matches_the_header():
     # int32 B,H,D,dtype; int64 stride_b,stride_h,stride_n; float scale (+ padding); pointer seq_len;
-    # float dropout_p; uint32 dropout_seed; int32 leave_unkept (+ padding)
+    # float dropout_p; uint32 dropout_seed; int32 leave_unkept; int32 grad_dtype
     assert ctypes.sizeof(bpt.BptShape) == 72
     assert bpt.BptShape.dropout_p.offset == 56 and bpt.BptShape.dropout_seed.offset == 60
-    assert bpt.BptShape.leave_unkept.offset == 64
+    assert bpt.BptShape.leave_unkept.offset == 64 and bpt.BptShape.grad_dtype.offset == 68
     assert bpt.BptShape.stride_b.offset == 16 and bpt.BptShape.scale.offset == 40
     assert bpt.BptShape.seq_len.offset == 48
 

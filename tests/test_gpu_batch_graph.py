@@ -146,6 +146,12 @@ def run_attention_case(dtype, n, k, causal, H, lengths, node_major=False, seed=5
         res[name] = float(np.abs(got - ref[name]).max())
         assert res[name] <= TOL[dtype], (name, res[name])
     say("   max-abs errors", {key: float("%.3g" % v) for key, v in res.items()})
+    if dtype == "bf16":   # gradients rounded to bf16: the same sums, rounded once
+        g16 = bpt.bpt_attn_bwd(g, Q, K, V, R, lse_d, dO, scale=scale, bf16_grads=True)
+        torch.cuda.synchronize()
+        for a32, a16 in zip(grads[:3], g16[:3]):
+            assert torch.equal(a32.to(torch.bfloat16), a16)
+        assert torch.equal(grads[3], g16[3])
     g.destroy()
 
 

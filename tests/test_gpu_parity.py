@@ -555,6 +555,76 @@ def test_run_to_run_reproducibility():
     g.destroy()
 
 
+BF16_GRADS = [
+    # (n, k, causal, B, H, lengths, leave_unkept, node_major, dQ in one rounding)
+    (16, 1, False, 2, 2, None, False, False, True),              # gather kernels
+    (1024, 4, False, 2, 2, None, False, False, True),            # token tiles with dense dS, key tiles chained
+    (4096, 8, True, 1, 2, None, False, True, True),              # the language-model density, node-major memory
+    (4096, 16, False, 1, 1, None, False, False, False),          # more than 128 ids: rel_grad_tile_kernel adds to dQ
+    (2048, 40, False, 1, 1, None, False, False, False),          # key tiles with table operands parked in LDS
+    (512, 4, False, 3, 2, [512, 300, 33], False, False, True),   # lengths, zero rows
+    (4096, 8, True, 2, 1, [3000, 129], True, False, True),       # lengths, rows left unwritten
+]
+
+
+@pytest.mark.parametrize("n,k,causal,B,H,lengths,leave,node_major,single", BF16_GRADS)
+def test_gradients_rounded_to_bf16(n, k, causal, B, H, lengths, leave, node_major, single):
+    # bpt_shape_t.grad_dtype = BPT_BF16: dQ, dK, dV are the fp32 sums of the default call rounded to nearest even
+    # once -- bit for bit -- except that dQ is rounded twice where a second kernel adds the relative-position part
+    # to it (graphs with more than 128 ids in use); d_rel does not depend on the option
+    say("bf16 gradients", n, k, causal, B, H, lengths, leave, node_major)
+    w = Workload("bf16_grads", 31, n, k, causal, B, H, 64, "bf16", True)
+    x = make_inputs(w)
+    g = bpt.bpt_build_graph(n, k, causal)
+    if node_major:
+        Q, K, V, dO = (to_dev(np.transpose(x[k_], (0, 2, 1, 3)), "bf16").transpose(1, 2) for k_ in ("Q", "K", "V", "dO"))
+    else:
+        Q, K, V, dO = (to_dev(x[k_], "bf16") for k_ in ("Q", "K", "V", "dO"))
+    R = to_dev(x["Rel"], "bf16")
+    lens_d = torch.tensor(lengths, dtype=torch.int32, device="cuda") if lengths else None
+    out, lse = bpt.bpt_attn_fwd(g, Q, K, V, R, scale=w.scale, seq_len=lens_d)
+    mark = 3.0
+    g32 = tuple(torch.full_like(Q, mark, dtype=torch.float32) for _ in range(3)) + (torch.empty_like(R, dtype=torch.float32),)
+    g16 = tuple(torch.full_like(Q, mark) for _ in range(3)) + (torch.empty_like(R, dtype=torch.float32),)
+    bpt.bpt_attn_bwd(g, Q, K, V, R, lse, dO, scale=w.scale, seq_len=lens_d, leave_unkept=leave, grads=g32)
+    bpt.bpt_attn_bwd(g, Q, K, V, R, lse, dO, scale=w.scale, seq_len=lens_d, leave_unkept=leave, grads=g16)
+    torch.cuda.synchronize()
+    assert g16[0].dtype == torch.bfloat16 and g16[0].stride() == Q.stride()
+    assert torch.equal(g32[3], g16[3])
+    for name, a32, a16 in zip(("dQ", "dK", "dV"), g32[:3], g16[:3]):
+        want = a32.to(torch.bfloat16)
+        if name == "dQ" and not single:
+            # the first kernel's part of a sum is rounded at its own size, which cancellation can leave above the sum's
+            bound = want.float().abs() * 2.0 ** -7 + float(want.float().abs().max()) * 2.0 ** -8
+            assert bool(((a16.float() - want.float()).abs() <= bound).all()), name
+            assert float((a16 == want).float().mean()) > 0.5, name
+        else:
+            assert torch.equal(a16, want), name
+    # the two-stage calls take the option too
+    dq2, dk2, dv2 = (torch.full_like(Q, mark) for _ in range(3))
+    ws = torch.empty(bpt.workspace_bytes(g, Q, w.scale)[1] + 256, dtype=torch.uint8, device="cuda")
+    bpt.bpt_attn_bwd_query_side(g, Q, K, V, R, lse, dO, dq2, g16[3], ws, scale=w.scale, seq_len=lens_d, leave_unkept=leave)
+    bpt.bpt_attn_bwd_key_side(g, Q, K, V, R, lse, dO, dk2, dv2, ws, scale=w.scale, seq_len=lens_d, leave_unkept=leave)
+    torch.cuda.synchronize()
+    assert torch.equal(dq2, g16[0]) and torch.equal(dk2, g16[1]) and torch.equal(dv2, g16[2])
+    with pytest.raises(ValueError):                      # all three of one type
+        bpt.bpt_attn_bwd(g, Q, K, V, R, lse, dO, scale=w.scale, grads=(g16[0], g32[1], g32[2], g32[3]))
+    g.destroy()
+
+
+def test_bf16_gradients_are_for_bf16_tensors():
+    g = bpt.bpt_build_graph(64, 2, False)
+    Q = torch.zeros(1, 1, g.num_nodes, 64, device="cuda")
+    R = torch.zeros(g.num_levels, g.rel_width, 64, device="cuda")
+    out, lse = bpt.bpt_attn_fwd(g, Q, Q, Q, R)
+    with pytest.raises(ValueError):
+        bpt.bpt_attn_bwd(g, Q, Q, Q, R, lse, Q, bf16_grads=True)
+    shp = bpt._shape_of(g, Q, None, bf16_grads=True)      # the C side refuses the combination as well
+    L = bpt.load_library()
+    assert L.bpt_attn_bwd_workspace(g.handle, __import__("ctypes").byref(shp)) == 2 ** 64 - 1
+    g.destroy()
+
+
 def test_invalid_arguments_on_device():
     g = bpt.bpt_build_graph(64, 2, False)
     Q = torch.zeros(1, 1, g.num_nodes, 64, device="cuda")
