@@ -50,6 +50,10 @@ struct AttnArgs {
     float drop_inv_keep;    // 1 / (1 - p)
     int32_t* queue;         // backward workspace: task counters of the key-tile kernel
     int32_t grad_bf16;      // dQ, dK, dV leave rounded to bf16 (the three pointers then address bf16 elements)
+    // packed batch on the tile kernels: delta[level][sequence] or null; lse of (bh, node u) at
+    // (bh / H) * lse_sb + (bh % H) * lse_sh + row of u
+    const int32_t* delta;
+    int64_t lse_sb, lse_sh;
 };
 
 // ---- dropout on the attention weights ---------------------------------------------------
@@ -105,6 +109,25 @@ __device__ __forceinline__ int node_first_token(int id, int lg) {
     const int level = lg - (31 - __clz(x - 1));
     return (((2 << lg) >> level) - x) << level;
 }
+// Rows of a packed batch (one graph for a batch of sequences, rows only for kept nodes): node (level l, index m) of
+// sequence b is row first_row[l][b] + m, that is its id in the tree over n plus delta[l][b] with
+// delta[l][b] = first_row[l][b] - (first id of level l).  The tile kernels keep walking the tree of one sequence
+// (ids, tile metadata, lengths) and translate an id only where a row of a caller's tensor is addressed: lane l of a
+// wavefront holds delta[l][b] of the sequence it works on (`dvec`), and the level of a node follows from its id.
+__device__ __forceinline__ int node_level(int id, int lg) {
+    const int x = (2 << lg) - id;                  // (n >> l) < x <= (2n >> l) on level l
+    return lg - (31 - __clz(x - 1));
+}
+__device__ __forceinline__ int load_delta(const int32_t* delta, int nbatch, int b, int lane, int levels) {
+    return lane < levels ? delta[lane * nbatch + b] : 0;
+}
+// the row of node `id` (any lane-varying id); dvec as loaded by load_delta
+__device__ __forceinline__ int packed_row(int id, int lg, int dvec) { return id + __shfl(dvec, node_level(id, lg)); }
+// delta of a level that is the same in all lanes
+__device__ __forceinline__ int level_delta(int dvec, int level) {
+    return __builtin_amdgcn_readlane(dvec, __builtin_amdgcn_readfirstlane(level));
+}
+
 // whether a sequence of `len` tokens keeps `node`.  Without seq_len every row of the graph is a kept node (also
 // in the graph of a packed batch, whose rows are not the nodes of one tree).
 __device__ __forceinline__ bool node_kept(const AttnArgs& a, int node, int len) {

@@ -38,6 +38,7 @@ struct KeyArgs {
     const int32_t* seq_len;   // [B] tokens of every sequence, or null
     int32_t leave_unkept;     // rows of nodes a shorter sequence does not keep: left unwritten instead of zero-filled
     int32_t grad_bf16;        // dK, dV leave rounded to bf16
+    const int32_t* delta;     // packed batch: delta[level][sequence] (see attn_device.h), or null
     int32_t n;
     uint32_t drop_thr, drop_seed;   // dropout on the attention weights (DROP variants)
     float drop_inv_keep;
@@ -52,7 +53,8 @@ __global__ void zero_ints_kernel(int32_t* p, int count) {
     if (i < count) p[i] = 0;
 }
 
-template <int NBC, bool DROP>
+// PACKED: the rows of the caller's tensors are those of a packed batch (KeyArgs.delta; see attn_device.h)
+template <int NBC, bool DROP, bool PACKED = false>
 __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int lane = threadIdx.x & 63;
@@ -114,6 +116,11 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyA
         if (kept_keys <= 0) continue;
         const rsrc_t rQ = make_rsrc(a.Q + base, a.slab_bytes), rG = make_rsrc(a.dout + base, a.slab_bytes);
         const rsrc_t rS = make_rsrc(a.stat + (int64_t)bh * a.N, (uint32_t)a.N * 8u);
+        // packed batch: rows of the caller's tensors are node ids moved by the sequence's delta of the node's level
+        // (`stat` is workspace and stays indexed by node id); keys the sequence does not keep have no row
+        const int dvec = PACKED ? load_delta(a.delta, a.BH / a.H, bh / a.H, lane, a.num_levels) : 0;
+        const int dlev = PACKED ? level_delta(dvec, level) : 0;
+        const int nstore = PACKED ? min(nkeys, kept_keys) : nkeys;
 
         // Software pipeline over pairs of chunks.  `Idx` = what has to be known before a pair's
         // rows can be requested (its column ids and map words); the rows of pair i+1 are
@@ -144,7 +151,8 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyA
             for (int ci = 0; ci < 2; ++ci)
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
-                    const int off = (int)__umul24(node[ci][h], a.row_bytes) + piece * 16;
+                    const int row = PACKED ? packed_row(node[ci][h], a.num_levels - 1, dvec) : node[ci][h];
+                    const int off = (int)__umul24(row, a.row_bytes) + piece * 16;
                     buf_row(rQ, off, qa[ci][h]);
                     buf_row(rG, off, ga[ci][h]);
                     stn[ci][h] = buf_f2(rS, node[ci][h] * 8);
@@ -154,7 +162,7 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyA
         load_idx(0);
 
         // B operands: the tile's keys (lane j <-> key j) and the rows of the table this level can meet
-        const int64_t krow = base + (int64_t)(node0 + min(j, nkeys - 1)) * a.sn + 16 * g;
+        const int64_t krow = base + (int64_t)(node0 + dlev + min(j, nstore - 1)) * a.sn + 16 * g;
         const bf16x8_t kb0 = load_once16<bf16x8_t>(a.K + krow);
         const bf16x8_t kb1 = load_once16<bf16x8_t>(a.K + krow + 8);
         const bf16x8_t vb0 = load_once16<bf16x8_t>(a.V + krow);
@@ -319,19 +327,19 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyA
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 const int idx = lane + 64 * i, key = idx >> 5, q4 = (idx & 31) * 4;
-                if (key < nkeys)
-                    store_grad4(q4 < kD ? a.dK : a.dV, base + (int64_t)(node0 + key) * a.sn + (q4 & (kD - 1)),
+                if (key < nstore)
+                    store_grad4(q4 < kD ? a.dK : a.dV, base + (int64_t)(node0 + dlev + key) * a.sn + (q4 & (kD - 1)),
                                 *reinterpret_cast<const float4*>(o_s + key * kKvOutStride + q4), true);
             }
         } else {
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 const int idx = lane + 64 * i, key = idx >> 5, q4 = (idx & 31) * 4;
-                if (key < nkeys) {
+                if (key < (part < 0 ? nstore : nkeys)) {
                     const float4 v = *reinterpret_cast<const float4*>(o_s + key * kKvOutStride + q4);
                     float* dst;
                     if (part < 0)
-                        dst = (q4 < kD ? a.dK + q4 : a.dV + (q4 - kD)) + base + (int64_t)(node0 + key) * a.sn;
+                        dst = (q4 < kD ? a.dK + q4 : a.dV + (q4 - kD)) + base + (int64_t)(node0 + dlev + key) * a.sn;
                     else
                         dst = a.part + (((int64_t)bh * a.num_part + part) * 16 + key) * (2 * kD) + q4;
                     if (part < 0)
@@ -358,7 +366,7 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyA
 // in lane (g, j), register r, and the lane that needs it reads it from there (ds_bpermute), which makes room
 // for the staging area.
 // G16: dK and dV leave rounded to bf16 (a compile-time switch: the stores sit inside the pipelined loop)
-template <int NBC, bool DROP, bool G16>
+template <int NBC, bool DROP, bool G16, bool PACKED = false>
 __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_chain_kernel(const KeyArgs a) {
     static_assert(NBC == 1 || NBC == 2, "the bias is looked up across the 16 lanes of a group, for up to two chunks of ids");
     extern __shared__ __align__(16) unsigned char smem[];
@@ -402,6 +410,9 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_chain_kernel(const Key
         const rsrc_t rQ = make_rsrc(a.Q + base, a.slab_bytes), rG = make_rsrc(a.dout + base, a.slab_bytes);
         const rsrc_t rK = make_rsrc(a.K + base, a.slab_bytes), rV = make_rsrc(a.V + base, a.slab_bytes);
         const rsrc_t rS = make_rsrc(a.stat + (int64_t)bh * a.N, (uint32_t)a.N * 8u);
+        // packed batch: see bwd_kv_tile_kernel
+        const int dvec = PACKED ? load_delta(a.delta, a.BH / a.H, bh / a.H, lane, a.num_levels) : 0;
+        const int dlev = PACKED ? level_delta(dvec, level) : 0;
 
         int node[2][2];
         uint2 mpn[2];
@@ -425,7 +436,8 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_chain_kernel(const Key
             for (int ci = 0; ci < 2; ++ci)
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
-                    const int off = (int)__umul24(node[ci][h], a.row_bytes) + piece * 16;
+                    const int row = PACKED ? packed_row(node[ci][h], a.num_levels - 1, dvec) : node[ci][h];
+                    const int off = (int)__umul24(row, a.row_bytes) + piece * 16;
                     buf_row(rQ, off, qa[ci][h]);
                     buf_row(rG, off, ga[ci][h]);
                     stn[ci][h] = buf_f2(rS, node[ci][h] * 8);
@@ -435,7 +447,7 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_chain_kernel(const Key
         // B operands: the keys of a tile (lane j <-> key j) ...
         Row<bf16_t> kk[2], vv[2], kn[2], vn[2];
         auto load_keys = [&](int first, int count, Row<bf16_t> (&ko)[2], Row<bf16_t> (&vo)[2]) {
-            const int off = (int)__umul24(first + min(j, count - 1), a.row_bytes) + 32 * g;
+            const int off = (int)__umul24(first + dlev + min(j, count - 1), a.row_bytes) + 32 * g;
             buf_row(rK, off, ko[0]);
             buf_row(rK, off + 16, ko[1]);
             buf_row(rV, off, vo[0]);
@@ -466,7 +478,7 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_chain_kernel(const Key
         for (int f = 0; f < 4; ++f) dk[f] = dv[f] = f32x4_t{0.f, 0.f, 0.f, 0.f};
         // sums of a finished tile wait in o_s for the next iteration: where they go
         bool staged = false;
-        int st_node0 = 0, st_nkeys = 0;
+        int st_node0 = 0, st_nkeys = 0;   // st_node0: first row of the finished tile's keys in dK, dV; st_nkeys: rows to store
         auto store_staged = [&]() {
             if (G16 && part < 0) {   // rounded to bf16: 8 bytes per lane, rows of 256 contiguous bytes
 #pragma unroll
@@ -608,8 +620,9 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_chain_kernel(const Key
                         dk[f][r] = dv[f][r] = 0.f;
                     }
                 staged = true;
-                st_node0 = node0;
-                st_nkeys = nkeys;
+                st_node0 = node0 + dlev;
+                // (packed batch: keys the sequence does not keep have no row; partial sums keep all of the tile's keys)
+                st_nkeys = PACKED && part < 0 ? min(nkeys, kept_keys) : nkeys;
                 if (c2 + 2 < nch) {   // on to the next tile of the task
                     ++kt;
                     node0 = uniform_i32(a.tile_node0, kt);
@@ -635,6 +648,7 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_chain_kernel(const Key
 // tile's keys in task order.  One workgroup per (batch*head, tile); thread -> (key, feature).
 // The workgroups after those write the zero gradients of the nodes no one attends to
 // (levels above the coarsest contextual level, from `first_zero` on).
+template <bool PACKED>
 __global__ void __launch_bounds__(256) kv_tile_merge_kernel(const KeyArgs a, const int32_t* __restrict__ multi_tile,
                                                             const int32_t* __restrict__ multi_ptr, int num_multi,
                                                             int first_zero) {
@@ -664,7 +678,9 @@ __global__ void __launch_bounds__(256) kv_tile_merge_kernel(const KeyArgs a, con
             if (todo) todo &= todo - 1;
             const int r = lane < 32 ? ra : rb;
             if (r >= 0) {
-                store_grad4((lane & 16) ? a.dV : a.dK, base + (int64_t)(first + r) * a.sn + 4 * (lane & 15),
+                int at = first + r;
+                if (PACKED) at += a.delta[node_level(at, a.num_levels - 1) * (a.BH / a.H) + bh / a.H];   // its packed row
+                store_grad4((lane & 16) ? a.dV : a.dK, base + (int64_t)at * a.sn + 4 * (lane & 15),
                             make_float4(0.f, 0.f, 0.f, 0.f), a.grad_bf16);
             }
         }
@@ -676,11 +692,15 @@ __global__ void __launch_bounds__(256) kv_tile_merge_kernel(const KeyArgs a, con
     const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
     // a tile none of whose keys exists in this (shorter) sequence has no partial sums: zeros
     const int len = seq_length(a.seq_len, bh / a.H, a.n);
-    const bool gone = ((len + (1 << level) - 1) >> level) - (node0 - (2 * a.n - ((2 * a.n) >> level))) <= 0;
+    const int kept_keys = ((len + (1 << level) - 1) >> level) - (node0 - (2 * a.n - ((2 * a.n) >> level)));
+    const bool gone = kept_keys <= 0;
     if (gone && a.leave_unkept) return;   // uniform for the workgroup
+    // packed batch: the tile's keys begin at the sequence's delta of the level; keys it does not keep have no row
+    const int dlev = PACKED ? a.delta[level * (a.BH / a.H) + bh / a.H] : 0;
+    const int nstore = PACKED ? min(nkeys, kept_keys) : nkeys;
     // thread -> (key, 4 consecutive values of its 64 dK | 64 dV); four partial sums in flight, combined in a fixed order
     const int p0 = gone ? multi_ptr[mt + 1] : multi_ptr[mt], p1 = multi_ptr[mt + 1];
-    for (int i = threadIdx.x; i < nkeys * 32; i += blockDim.x) {
+    for (int i = threadIdx.x; i < nstore * 32; i += blockDim.x) {
         const int key = i >> 5, q4 = (i & 31) * 4;
         const float* src = a.part + (((int64_t)bh * a.num_part) * 16 + key) * (2 * kD) + q4;
         const int64_t pstride = (int64_t)16 * 2 * kD;
@@ -702,7 +722,7 @@ __global__ void __launch_bounds__(256) kv_tile_merge_kernel(const KeyArgs a, con
         }
         const float4 t = make_float4((s0.x + s1.x) + (s2.x + s3.x), (s0.y + s1.y) + (s2.y + s3.y),
                                      (s0.z + s1.z) + (s2.z + s3.z), (s0.w + s1.w) + (s2.w + s3.w));
-        store_grad4(q4 < kD ? a.dK : a.dV, base + (int64_t)(node0 + key) * a.sn + (q4 & (kD - 1)), t, a.grad_bf16);
+        store_grad4(q4 < kD ? a.dK : a.dV, base + (int64_t)(node0 + dlev + key) * a.sn + (q4 & (kD - 1)), t, a.grad_bf16);
     }
 }
 

@@ -37,6 +37,10 @@ struct SpanArgs {
     const int32_t* seq_len;   // [B] tokens of every sequence, or null
     int32_t leave_unkept;     // rows of nodes a shorter sequence does not keep: left unwritten instead of zero-filled
     int32_t grad_bf16;        // dQ leaves rounded to bf16
+    // packed batch: delta[level][sequence] (see attn_device.h) or null; lse of (bh, node u) is at
+    // (bh / H) * lse_sb + (bh % H) * lse_sh + row of u
+    const int32_t* delta;
+    int64_t lse_sb, lse_sh;
     uint32_t drop_thr, drop_seed;   // dropout on the attention weights (DROP variants)
     float drop_inv_keep;
 };
@@ -60,6 +64,27 @@ __device__ __forceinline__ int span_slot_node(int group, int slot, int L, int n,
     bool valid;
     span_slot(group, slot, L, level, loc, valid);
     return span_level_offset(n, level) + (t0 >> level) + loc;
+}
+// the same as a row of the caller's tensors: the node id, or in a packed batch (dvec: this lane's delta of the
+// sequence) the node's packed row
+template <bool PACKED>
+__device__ __forceinline__ int span_slot_row(const SpanArgs& a, int group, int slot, int t0, int dvec) {
+    int level, loc;
+    bool valid;
+    span_slot(group, slot, a.L, level, loc, valid);
+    const int node = span_level_offset(a.n, level) + (t0 >> level) + loc;
+    return PACKED ? node + __shfl(dvec, level) : node;
+}
+// whether a sequence of len tokens keeps the node of the slot (its first token exists)
+__device__ __forceinline__ bool span_slot_kept(const SpanArgs& a, int group, int slot, int t0, int len) {
+    int level, loc;
+    bool valid;
+    span_slot(group, slot, a.L, level, loc, valid);
+    return valid && ((((t0 >> level) + loc) << level) < len);
+}
+template <bool PACKED>
+__device__ __forceinline__ int64_t span_lse_at(const SpanArgs& a, int bh) {
+    return PACKED ? (int64_t)(bh / a.H) * a.lse_sb + (int64_t)(bh % a.H) * a.lse_sh : (int64_t)bh * a.N;
 }
 // scale * log2(e) * q . r_anc(level) for the query of this lane's column: every lane holds 16
 // features of its query (the B operand), the four lane groups hold the four quarters
@@ -89,7 +114,7 @@ __device__ __forceinline__ void span_block_gone(const SpanArgs& a, int bh, int t
             if (a.leave_unkept) continue;
             for (int i = lane; i < cnt * 8; i += 64)     // 64 bf16 per row
                 *reinterpret_cast<uint4*>(a.out + base + (int64_t)(node0 + (i >> 3)) * a.sn + (i & 7) * 8) = make_uint4(0u, 0u, 0u, 0u);
-            if (lane < cnt) a.lse[(int64_t)bh * a.N + node0 + lane] = 0.f;
+            if (lane < cnt) a.lse[(int64_t)bh * a.N + node0 + lane] = 0.f;   // (never with a packed batch: leave_unkept)
         } else {
             if (!a.leave_unkept)
                 for (int i = lane; i < cnt * 16; i += 64)    // 64 floats per row
@@ -99,7 +124,8 @@ __device__ __forceinline__ void span_block_gone(const SpanArgs& a, int bh, int t
     }
 }
 
-template <bool DROP>
+// PACKED: the rows of the caller's tensors are those of a packed batch (SpanArgs.delta; see attn_device.h)
+template <bool DROP, bool PACKED = false>
 __global__ void __launch_bounds__(kTileThreads) fwd_span_tile_kernel(const SpanArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int lane = threadIdx.x & 63;
@@ -121,6 +147,10 @@ __global__ void __launch_bounds__(kTileThreads) fwd_span_tile_kernel(const SpanA
         span_block_gone(a, bh, t0, base, true, lane);
         return;
     }
+    // packed batch: rows of the caller's tensors are the node ids moved by the sequence's delta of the node's level;
+    // a node the sequence does not keep has no row, its loads go to the last kept node of its level instead (every
+    // score of such a query, and of such a token, is masked) and nothing is stored for it
+    const int dvec = PACKED ? load_delta(a.delta, a.BH / a.H, bh / a.H, lane, a.L + 1) : 0;
     // the query rows of all three groups are asked for together with the block's K and V: one round trip
     // to memory per block instead of four
     bf16x8_t qall[3][2];
@@ -129,14 +159,20 @@ __global__ void __launch_bounds__(kTileThreads) fwd_span_tile_kernel(const SpanA
         int level, loc;
         bool valid;
         span_slot(min(grp, ngroups - 1), j, a.L, level, loc, valid);
-        const bf16_t* qrow = a.Q + base + (int64_t)(span_level_offset(a.n, level) + (t0 >> level) + loc) * a.sn + 16 * g;
+        int idx = (t0 >> level) + loc, shift_row = 0;
+        if (PACKED) {
+            idx = min(idx, ((len + (1 << level) - 1) >> level) - 1);
+            shift_row = __shfl(dvec, level);
+        }
+        const bf16_t* qrow = a.Q + base + (int64_t)(span_level_offset(a.n, level) + idx + shift_row) * a.sn + 16 * g;
         qall[grp][0] = *reinterpret_cast<const bf16x8_t*>(qrow);
         qall[grp][1] = *reinterpret_cast<const bf16x8_t*>(qrow + 8);
     }
     bf16x8_t ka[2][2];
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
-        const int64_t at = base + (int64_t)(t0 + 16 * c + j) * a.sn + 16 * g;
+        const int tk = PACKED ? min(t0 + 16 * c + j, len - 1) + level_delta(dvec, 0) : t0 + 16 * c + j;
+        const int64_t at = base + (int64_t)tk * a.sn + 16 * g;
         ka[c][0] = *reinterpret_cast<const bf16x8_t*>(a.K + at);
         ka[c][1] = *reinterpret_cast<const bf16x8_t*>(a.K + at + 8);
         const uint4 v0 = *reinterpret_cast<const uint4*>(a.V + at), v1 = *reinterpret_cast<const uint4*>(a.V + at + 8);
@@ -206,13 +242,18 @@ __global__ void __launch_bounds__(kTileThreads) fwd_span_tile_kernel(const SpanA
         // C[m = query][n = feature]: this lane holds queries 4g..4g+3, feature 16f + j
         if (grp < 2) {
             // l == 0: a span past the end of a shorter sequence, its row is zero
-            if (g == 0 && valid) a.lse[(int64_t)bh * a.N + node] = l > 0.f ? (m + fast_log2(l)) * kLn2 : 0.f;
+            constexpr bool guard = PACKED;
+            const int lse_row = PACKED ? node + __shfl(dvec, level) : node;   // (all lanes take part in the exchange)
+            if (g == 0 && valid && !(guard && l <= 0.f))
+                a.lse[span_lse_at<PACKED>(a, bh) + lse_row] = l > 0.f ? (m + fast_log2(l)) * kLn2 : 0.f;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int slot = 4 * g + r;
                 const float lq = __shfl(l, slot);
+                const int orow_at = span_slot_row<PACKED>(a, grp, slot, t0, dvec);
                 if (grp == 1 && slot == 15) continue;
-                bf16_t* orow = a.out + base + (int64_t)span_slot_node(grp, slot, a.L, a.n, t0) * a.sn + j;
+                if (guard && lq <= 0.f) continue;   // a span past the end of the sequence has no row
+                bf16_t* orow = a.out + base + (int64_t)orow_at * a.sn + j;
                 const float inv = lq > 0.f ? 1.f / lq : 0.f;
 #pragma unroll
                 for (int f = 0; f < 4; ++f) store_once(&orow[16 * f], (bf16_t)to_bf16_bits(o[f][r] * inv));
@@ -271,13 +312,25 @@ __device__ __forceinline__ bool span_merge_row(const SpanArgs& a, int item, int 
     return true;
 }
 
+// the row of a merged node in the caller's tensors: its id, or its packed row (a merged row with partials is kept)
+template <bool PACKED>
+__device__ __forceinline__ int span_merged_row(const SpanArgs& a, const SpanRow& r) {
+    if (!PACKED) return r.v;
+    int level, mi;
+    span_node_level(a.n, a.L, r.v, level, mi);
+    return r.v + a.delta[level * (a.BH / a.H) + r.bh / a.H];
+}
+
 // lse * log2(e) of a merged row for the key side, kLseGone if the sequence does not keep the node
+template <bool PACKED>
 __device__ __forceinline__ float span_row_lse2(const SpanArgs& a, const SpanRow& r) {
     int level, mi;
     span_node_level(a.n, a.L, r.v, level, mi);
-    return (mi << level) < seq_length(a.seq_len, r.bh / a.H, a.n) ? a.lse_r[(int64_t)r.bh * a.N + r.v] * kLog2e : kLseGone;
+    return (mi << level) < seq_length(a.seq_len, r.bh / a.H, a.n) ? a.lse_r[span_lse_at<PACKED>(a, r.bh) + span_merged_row<PACKED>(a, r)] * kLog2e
+                                                                   : kLseGone;
 }
 
+template <bool PACKED>
 __device__ __forceinline__ void fwd_span_merge_small(const SpanArgs& a, int item, int first, int rows) {
     const int lane = threadIdx.x & 63;
     SpanRow r;
@@ -302,19 +355,21 @@ __device__ __forceinline__ void fwd_span_merge_small(const SpanArgs& a, int item
         acc += o[b] * c;
     }
     const int64_t base = (int64_t)(r.bh / a.H) * a.sb + (int64_t)(r.bh % a.H) * a.sh;
-    store_once(&a.out[base + (int64_t)r.v * a.sn + lane], (bf16_t)to_bf16_bits(ls > 0.f ? acc / ls : 0.f));
-    if (lane == 0) a.lse[(int64_t)r.bh * a.N + r.v] = ls > 0.f ? (mx + fast_log2(ls)) * kLn2 : 0.f;
+    const int row = span_merged_row<PACKED>(a, r);
+    store_once(&a.out[base + (int64_t)row * a.sn + lane], (bf16_t)to_bf16_bits(ls > 0.f ? acc / ls : 0.f));
+    if (lane == 0) a.lse[span_lse_at<PACKED>(a, r.bh) + row] = ls > 0.f ? (mx + fast_log2(ls)) * kLn2 : 0.f;
 }
 
 // one kernel for both kinds of rows: the first `small_blocks` workgroups take 16 short rows each
 // (one per wavefront), the others one long row each
+template <bool PACKED>
 __global__ void __launch_bounds__(kSpanBigThreads) fwd_span_merge_kernel(const SpanArgs a, int first, int rows_small,
                                                                          int first_big, int rows_big, int small_blocks) {
     __shared__ float s_acc[64][kD + 4];
     __shared__ float s_l[64];
     __shared__ float s_m[kSpanBigThreads / 64];
     if ((int)blockIdx.x < small_blocks) {   // uniform for the workgroup; this path has no barrier
-        fwd_span_merge_small(a, blockIdx.x * (kSpanBigThreads / 64) + (threadIdx.x >> 6), first, rows_small);
+        fwd_span_merge_small<PACKED>(a, blockIdx.x * (kSpanBigThreads / 64) + (threadIdx.x >> 6), first, rows_small);
         return;
     }
     SpanRow r;
@@ -353,8 +408,9 @@ __global__ void __launch_bounds__(kSpanBigThreads) fwd_span_merge_kernel(const S
             lt += s_l[p];
         }
         const int64_t base = (int64_t)(r.bh / a.H) * a.sb + (int64_t)(r.bh % a.H) * a.sh;
-        store_once(&a.out[base + (int64_t)r.v * a.sn + t], (bf16_t)to_bf16_bits(lt > 0.f ? sum / lt : 0.f));
-        if (t == 0) a.lse[(int64_t)r.bh * a.N + r.v] = lt > 0.f ? (mx + fast_log2(lt)) * kLn2 : 0.f;
+        const int row = span_merged_row<PACKED>(a, r);
+        store_once(&a.out[base + (int64_t)row * a.sn + t], (bf16_t)to_bf16_bits(lt > 0.f ? sum / lt : 0.f));
+        if (t == 0) a.lse[span_lse_at<PACKED>(a, r.bh) + row] = lt > 0.f ? (mx + fast_log2(lt)) * kLn2 : 0.f;
     }
 }
 
@@ -363,7 +419,7 @@ __global__ void __launch_bounds__(kSpanBigThreads) fwd_span_merge_kernel(const S
 // and dS = w - delta p are final and dQ = scale * dS K_block (r_anc drops out: the dS of a row
 // sum to zero).  An ancestor stores the partial sums A = W K, Bv = P K, delta, which the merge
 // kernel turns into dQ = scale * (sum A - delta * sum Bv).
-template <bool DROP, bool G16>   // G16: dQ leaves rounded to bf16
+template <bool DROP, bool G16, bool PACKED = false>   // G16: dQ leaves rounded to bf16
 __global__ void __launch_bounds__(kTileThreads, 3) bwd_q_span_tile_kernel(const SpanArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int lane = threadIdx.x & 63;
@@ -384,6 +440,8 @@ __global__ void __launch_bounds__(kTileThreads, 3) bwd_q_span_tile_kernel(const 
         span_block_gone(a, bh, t0, base, false, lane);
         return;
     }
+    // packed batch: see fwd_span_tile_kernel
+    const int dvec = PACKED ? load_delta(a.delta, a.BH / a.H, bh / a.H, lane, a.L + 1) : 0;
     // the Q and dO rows and the lse of all three groups are asked for together with the block's K and V:
     // one round trip to memory per block instead of four
     bf16x8_t qall[3][2], gall[3][2];
@@ -393,19 +451,25 @@ __global__ void __launch_bounds__(kTileThreads, 3) bwd_q_span_tile_kernel(const 
         int level, loc;
         bool valid;
         span_slot(min(grp, ngroups - 1), j, a.L, level, loc, valid);
-        const int node = span_level_offset(a.n, level) + (t0 >> level) + loc;
-        const bf16_t* qrow = a.Q + base + (int64_t)node * a.sn + 16 * g;
-        const bf16_t* grow = a.dout + base + (int64_t)node * a.sn + 16 * g;
+        int idx = (t0 >> level) + loc, shift_row = 0;
+        if (PACKED) {
+            idx = min(idx, ((len + (1 << level) - 1) >> level) - 1);
+            shift_row = __shfl(dvec, level);
+        }
+        const int row = span_level_offset(a.n, level) + idx + shift_row;
+        const bf16_t* qrow = a.Q + base + (int64_t)row * a.sn + 16 * g;
+        const bf16_t* grow = a.dout + base + (int64_t)row * a.sn + 16 * g;
         qall[grp][0] = *reinterpret_cast<const bf16x8_t*>(qrow);
         qall[grp][1] = *reinterpret_cast<const bf16x8_t*>(qrow + 8);
         gall[grp][0] = *reinterpret_cast<const bf16x8_t*>(grow);
         gall[grp][1] = *reinterpret_cast<const bf16x8_t*>(grow + 8);
-        lall[grp] = a.lse_r[(int64_t)bh * a.N + node];
+        lall[grp] = a.lse_r[span_lse_at<PACKED>(a, bh) + row];
     }
     bf16x8_t ka[2][2], va[2][2];
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
-        const int64_t at = base + (int64_t)(t0 + 16 * c + j) * a.sn + 16 * g;
+        const int tk = PACKED ? min(t0 + 16 * c + j, len - 1) + level_delta(dvec, 0) : t0 + 16 * c + j;
+        const int64_t at = base + (int64_t)tk * a.sn + 16 * g;
         const uint4 k0 = *reinterpret_cast<const uint4*>(a.K + at), k1 = *reinterpret_cast<const uint4*>(a.K + at + 8);
         ka[c][0] = __builtin_bit_cast(bf16x8_t, k0);
         ka[c][1] = __builtin_bit_cast(bf16x8_t, k1);
@@ -471,12 +535,15 @@ __global__ void __launch_bounds__(kTileThreads, 3) bwd_q_span_tile_kernel(const 
             }
             if (g == 0 && valid)
                 a.stat[(int64_t)bh * a.N + node] = make_float2((((t0 >> level) + loc) << level) < len ? lse2 : kLseGone, dl);
+            constexpr bool guard = PACKED;   // packed batch: a span past the end of the sequence has no row
             if (G16) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int slot = 4 * g + r;
+                    const int row = span_slot_row<PACKED>(a, grp, slot, t0, dvec);
                     if (grp == 1 && slot == 15) continue;
-                    bf16_t* orow = reinterpret_cast<bf16_t*>(a.dQ) + base + (int64_t)span_slot_node(grp, slot, a.L, a.n, t0) * a.sn + j;
+                    if (guard && !span_slot_kept(a, grp, slot, t0, len)) continue;
+                    bf16_t* orow = reinterpret_cast<bf16_t*>(a.dQ) + base + (int64_t)row * a.sn + j;
 #pragma unroll
                     for (int f = 0; f < 4; ++f) store_once(&orow[16 * f], (bf16_t)to_bf16_bits(a.scale * dq[f][r]));
                 }
@@ -484,8 +551,10 @@ __global__ void __launch_bounds__(kTileThreads, 3) bwd_q_span_tile_kernel(const 
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int slot = 4 * g + r;
+                    const int row = span_slot_row<PACKED>(a, grp, slot, t0, dvec);
                     if (grp == 1 && slot == 15) continue;
-                    float* orow = a.dQ + base + (int64_t)span_slot_node(grp, slot, a.L, a.n, t0) * a.sn + j;
+                    if (guard && !span_slot_kept(a, grp, slot, t0, len)) continue;
+                    float* orow = a.dQ + base + (int64_t)row * a.sn + j;
 #pragma unroll
                     for (int f = 0; f < 4; ++f) store_once(&orow[16 * f], a.scale * dq[f][r]);
                 }
@@ -529,6 +598,7 @@ __global__ void __launch_bounds__(kTileThreads, 3) bwd_q_span_tile_kernel(const 
     }
 }
 
+template <bool PACKED>
 __device__ __forceinline__ void bwd_q_span_merge_small(const SpanArgs& a, int item, int first, int rows) {
     const int lane = threadIdx.x & 63;
     SpanRow r;
@@ -554,16 +624,17 @@ __device__ __forceinline__ void bwd_q_span_merge_small(const SpanArgs& a, int it
             dl += xd[b];
         }
     const int64_t base = (int64_t)(r.bh / a.H) * a.sb + (int64_t)(r.bh % a.H) * a.sh;
-    store_grad(a.dQ, base + (int64_t)r.v * a.sn + lane, a.scale * (sa - dl * sb), a.grad_bf16);
-    if (lane == 0) a.stat[(int64_t)r.bh * a.N + r.v] = make_float2(span_row_lse2(a, r), dl);
+    store_grad(a.dQ, base + (int64_t)span_merged_row<PACKED>(a, r) * a.sn + lane, a.scale * (sa - dl * sb), a.grad_bf16);
+    if (lane == 0) a.stat[(int64_t)r.bh * a.N + r.v] = make_float2(span_row_lse2<PACKED>(a, r), dl);
 }
 
+template <bool PACKED>
 __global__ void __launch_bounds__(kSpanBigThreads) bwd_q_span_merge_kernel(const SpanArgs a, int first, int rows_small,
                                                                            int first_big, int rows_big, int small_blocks) {
     __shared__ float s_a[64][kD + 4], s_b[64][kD + 4];
     __shared__ float s_d[64];
     if ((int)blockIdx.x < small_blocks) {
-        bwd_q_span_merge_small(a, blockIdx.x * (kSpanBigThreads / 64) + (threadIdx.x >> 6), first, rows_small);
+        bwd_q_span_merge_small<PACKED>(a, blockIdx.x * (kSpanBigThreads / 64) + (threadIdx.x >> 6), first, rows_small);
         return;
     }
     SpanRow r;
@@ -595,8 +666,8 @@ __global__ void __launch_bounds__(kSpanBigThreads) bwd_q_span_merge_kernel(const
             td += s_d[p];
         }
         const int64_t base = (int64_t)(r.bh / a.H) * a.sb + (int64_t)(r.bh % a.H) * a.sh;
-        store_grad(a.dQ, base + (int64_t)r.v * a.sn + t, a.scale * (ta - td * tb), a.grad_bf16);
-        if (t == 0) a.stat[(int64_t)r.bh * a.N + r.v] = make_float2(span_row_lse2(a, r), td);
+        store_grad(a.dQ, base + (int64_t)span_merged_row<PACKED>(a, r) * a.sn + t, a.scale * (ta - td * tb), a.grad_bf16);
+        if (t == 0) a.stat[(int64_t)r.bh * a.N + r.v] = make_float2(span_row_lse2<PACKED>(a, r), td);
     }
 }
 

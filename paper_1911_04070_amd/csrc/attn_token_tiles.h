@@ -55,6 +55,11 @@ struct TileArgs {
     int32_t leave_unkept;   // rows of nodes a shorter sequence does not keep: left unwritten instead of zero-filled
     int32_t grad_bf16;      // dQ leaves rounded to bf16
     int32_t n, k, W, ctx_levels, causal;
+    // packed batch: delta[level][sequence] (see attn_device.h) or null; lse of (batch*head index bh, node u) is at
+    // (bh / H) * lse_sb + (bh % H) * lse_sh + row of u
+    const int32_t* delta;
+    int32_t levels, lg;
+    int64_t lse_sb, lse_sh;
     // dropout on the attention weights (DROP variants of the kernels)
     uint32_t drop_thr, drop_seed;
     float drop_inv_keep;
@@ -182,12 +187,14 @@ __device__ __forceinline__ void nth_tile(const int* pref, int B, int H, int num_
 // Position of a wavefront in its sequence of (token tile, pair of chunks); wave-uniform.
 struct TileCursor {
     int t, pair, npairs, cp0, bh, tile;
+    int dvec;   // packed batch: this lane's delta of the sequence the tile belongs to (0 otherwise)
     bool valid;
 };
 
 // REL_LDS: the compact relative-position table is staged in LDS; otherwise (large tables) its rows
 // are read from memory when a tile forms its bias table.
-template <bool REL_LDS, bool DROP>
+// PACKED: the rows of the caller's tensors are those of a packed batch (TileArgs.delta; see attn_device.h)
+template <bool REL_LDS, bool DROP, bool PACKED = false>
 __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     bf16_t* rel_s = reinterpret_cast<bf16_t*>(smem);                                   // [cid_pad][kRelStride]
@@ -232,7 +239,7 @@ __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArg
         bf16_t* orow = a.out + base + (int64_t)(tile * 16 + r8) * a.sn + piece * 8;
         *reinterpret_cast<uint4*>(orow) = make_uint4(0u, 0u, 0u, 0u);
         *reinterpret_cast<uint4*>(orow + 8 * a.sn) = make_uint4(0u, 0u, 0u, 0u);
-        if (lane < 16) a.lse[(int64_t)bh * a.N + tile * 16 + lane] = 0.f;
+        if (lane < 16) a.lse[(int64_t)bh * a.N + tile * 16 + lane] = 0.f;   // (never with PACKED: its rows are left unwritten)
     };
     if (compact) {
         live_tiles_prefix(pref_s, a.seq_len, nbatch, a.n, a.num_tiles);
@@ -258,12 +265,14 @@ __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArg
         c.valid = false;
         c.pair = 0;
         c.npairs = 1;
+        c.dvec = 0;
         if (compact) {   // the next tile that exists; the walk covers nothing else
             const int idx = c.t * kTileWaves + wave;
             if (c.t < w.t_end && idx < live_total) {
                 nth_tile(pref_s, nbatch, a.H, a.num_tiles, false, idx, c.bh, c.tile);
                 c.cp0 = a.chunk_ptr[c.tile];
                 c.npairs = (a.chunk_ptr[c.tile + 1] - c.cp0) >> 1;
+                c.dvec = PACKED ? load_delta(a.delta, nbatch, c.bh / a.H, lane, a.levels) : 0;
                 c.valid = true;
             }
             return;
@@ -279,6 +288,7 @@ __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArg
             }
             c.cp0 = a.chunk_ptr[c.tile];
             c.npairs = (a.chunk_ptr[c.tile + 1] - c.cp0) >> 1;
+            c.dvec = PACKED ? load_delta(a.delta, nbatch, c.bh / a.H, lane, a.levels) : 0;
             c.valid = true;
             return;
         }
@@ -310,12 +320,16 @@ __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArg
         for (int ci = 0; ci < 2; ++ci)
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                const int off = (int)__umul24(node_n[ci][h], a.row_bytes) + piece * 16;
+                const int node = PACKED ? packed_row(node_n[ci][h], a.lg, c.dvec) : node_n[ci][h];
+                const int off = (int)__umul24(node, a.row_bytes) + piece * 16;
                 buf_row(rK, off, kr[ci][h]);
                 buf_row(rV, off, vr[ci][h]);
             }
         if (c.pair == 0) {   // token j, features 16g..16g+15
-            const int64_t at = base + (int64_t)(c.tile * 16 + j) * a.sn + 16 * g;
+            // (packed batch: a token past the end of the sequence reads the sequence's last row instead of another node's)
+            const int tq = PACKED ? min(c.tile * 16 + j, seq_length_u(a.seq_len, c.bh / a.H, a.n) - 1) + level_delta(c.dvec, 0)
+                                   : c.tile * 16 + j;
+            const int64_t at = base + (int64_t)tq * a.sn + 16 * g;
             qn0 = *reinterpret_cast<const bf16x8_t*>(a.Q + at);
             qn1 = *reinterpret_cast<const bf16x8_t*>(a.Q + at + 8);
         }
@@ -469,11 +483,17 @@ __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArg
             // row sums: token j is spread over the 4 lane groups
             float l = l_part + __shfl_xor(l_part, 16);
             l += __shfl_xor(l, 32);
-            if (g == 0) a.lse[(int64_t)cc.bh * a.N + t0 + j] = t0 + j < len ? (m_run + fast_log2(l)) * kLn2 : 0.f;
-            bf16_t* orow = a.out + base + (int64_t)t0 * a.sn + j;
+            // packed batch: the token rows of the sequence begin at row level_delta(.., 0), and a row past the end of
+            // the sequence is some other node's row: nothing is stored there
+            const int row0 = PACKED ? t0 + level_delta(cc.dvec, 0) : t0;
+            constexpr bool guard = PACKED;
+            const int64_t lse_at = PACKED ? (int64_t)(cc.bh / a.H) * a.lse_sb + (int64_t)(cc.bh % a.H) * a.lse_sh : (int64_t)cc.bh * a.N;
+            if (g == 0 && !(guard && t0 + j >= len)) a.lse[lse_at + row0 + j] = t0 + j < len ? (m_run + fast_log2(l)) * kLn2 : 0.f;
+            bf16_t* orow = a.out + base + (int64_t)row0 * a.sn + j;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const float inv = t0 + 4 * g + r < len ? 1.f / __shfl(l, 4 * g + r) : 0.f;
+                if (guard && t0 + 4 * g + r >= len) continue;
 #pragma unroll
                 for (int f = 0; f < 4; ++f)
                     store_once(&orow[(int64_t)(4 * g + r) * a.sn + 16 * f], (bf16_t)to_bf16_bits(o[f][r] * inv));
@@ -503,7 +523,7 @@ __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArg
 // transposing reads, into accumulators the wavefront keeps over all its tiles (at most kDenseChunks
 // chunks of 16 ids).  Nothing per slot or per tile leaves for a d_rel kernel; every workgroup writes
 // one copy of d_rel at the end, and drel_reduce_kernel adds the copies in a fixed order.
-template <bool REL_LDS, bool DROP, bool DENSE = false>
+template <bool REL_LDS, bool DROP, bool DENSE = false, bool PACKED = false>
 __global__ void __launch_bounds__(kTileThreads, DENSE ? 1 : 2) bwd_q_tile_kernel(const TileArgs a) {
     static_assert(!DENSE || REL_LDS, "the dense variant multiplies by the staged table");
     extern __shared__ __align__(16) unsigned char smem[];
@@ -583,12 +603,14 @@ __global__ void __launch_bounds__(kTileThreads, DENSE ? 1 : 2) bwd_q_tile_kernel
         c.valid = false;
         c.pair = 0;
         c.npairs = 1;
+        c.dvec = 0;
         if (compact) {   // the next tile that exists; the walk covers nothing else
             const int idx = c.t * kTileWaves + wave;
             if (c.t < w.t_end && idx < live_total) {
                 nth_tile(pref_s, nbatch, a.H, a.num_tiles, false, idx, c.bh, c.tile);
                 c.cp0 = uniform_i32(a.chunk_ptr, c.tile);
                 c.npairs = (uniform_i32(a.chunk_ptr, c.tile + 1) - c.cp0) >> 1;
+                c.dvec = PACKED ? load_delta(a.delta, nbatch, c.bh / a.H, lane, a.levels) : 0;
                 c.valid = true;
             }
             return;
@@ -604,6 +626,7 @@ __global__ void __launch_bounds__(kTileThreads, DENSE ? 1 : 2) bwd_q_tile_kernel
             }
             c.cp0 = uniform_i32(a.chunk_ptr, c.tile);
             c.npairs = (uniform_i32(a.chunk_ptr, c.tile + 1) - c.cp0) >> 1;
+            c.dvec = PACKED ? load_delta(a.delta, nbatch, c.bh / a.H, lane, a.levels) : 0;
             c.valid = true;
             return;
         }
@@ -636,17 +659,21 @@ __global__ void __launch_bounds__(kTileThreads, DENSE ? 1 : 2) bwd_q_tile_kernel
         for (int ci = 0; ci < 2; ++ci)
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                const int off = (int)__umul24(node_n[ci][h], a.row_bytes) + piece * 16;
+                const int node = PACKED ? packed_row(node_n[ci][h], a.lg, c.dvec) : node_n[ci][h];
+                const int off = (int)__umul24(node, a.row_bytes) + piece * 16;
                 buf_row(rK, off, kr[ci][h]);
                 buf_row(rV, off, vr[ci][h]);
             }
         if (c.pair == 0) {   // the tile's own rows: Q^T and dO^T operands (token j, features 16g..16g+15)
-            const int64_t at = base + (int64_t)(c.tile * 16 + j) * a.sn + 16 * g;
+            // (packed batch: a token past the end of the sequence reads the sequence's last row instead of another node's)
+            const int tq = PACKED ? min(c.tile * 16 + j, seq_length_u(a.seq_len, c.bh / a.H, a.n) - 1) + level_delta(c.dvec, 0)
+                                   : c.tile * 16 + j;
+            const int64_t at = base + (int64_t)tq * a.sn + 16 * g;
             qn0 = load_once16<bf16x8_t>(a.Q + at);
             qn1 = load_once16<bf16x8_t>(a.Q + at + 8);
             gn0 = load_once16<bf16x8_t>(a.dout + at);
             gn1 = load_once16<bf16x8_t>(a.dout + at + 8);
-            lse_n = a.lse_r[(int64_t)c.bh * a.N + c.tile * 16 + j];
+            lse_n = a.lse_r[(PACKED ? (int64_t)(c.bh / a.H) * a.lse_sb + (int64_t)(c.bh % a.H) * a.lse_sh : (int64_t)c.bh * a.N) + tq];
         }
     };
 
@@ -901,7 +928,9 @@ __global__ void __launch_bounds__(kTileThreads, DENSE ? 1 : 2) bwd_q_tile_kernel
                     }
                 wave_lds_sync();   // before the next tile clears the tables and forms its bias table
             }
-            const int64_t qrow_out = base + (int64_t)t0 * a.sn + j;
+            // packed batch: the sequence's token rows begin at row level_delta(.., 0); a row past its end is not stored
+            const int64_t qrow_out = base + (int64_t)(PACKED ? t0 + level_delta(cc.dvec, 0) : t0) * a.sn + j;
+            const int live = PACKED ? len - t0 : 16;   // rows of the tile that may be stored
             float dr[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) dr[r] = __shfl(delta, 4 * g + r);
@@ -909,17 +938,21 @@ __global__ void __launch_bounds__(kTileThreads, DENSE ? 1 : 2) bwd_q_tile_kernel
                 bf16_t* dst = reinterpret_cast<bf16_t*>(a.dQ) + qrow_out;
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
+                    if (4 * g + r < live) {
 #pragma unroll
-                    for (int f = 0; f < 4; ++f)
-                        store_once(&dst[(int64_t)(4 * g + r) * a.sn + 16 * f],
-                                   (bf16_t)to_bf16_bits(a.scale * (ow[f][r] - dr[r] * op[f][r] + dqr[f][r])));
+                        for (int f = 0; f < 4; ++f)
+                            store_once(&dst[(int64_t)(4 * g + r) * a.sn + 16 * f],
+                                       (bf16_t)to_bf16_bits(a.scale * (ow[f][r] - dr[r] * op[f][r] + dqr[f][r])));
+                    }
             } else {
                 float* dst = a.dQ + qrow_out;
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
+                    if (4 * g + r < live) {
 #pragma unroll
-                    for (int f = 0; f < 4; ++f)
-                        store_once(&dst[(int64_t)(4 * g + r) * a.sn + 16 * f], a.scale * (ow[f][r] - dr[r] * op[f][r] + dqr[f][r]));
+                        for (int f = 0; f < 4; ++f)
+                            store_once(&dst[(int64_t)(4 * g + r) * a.sn + 16 * f], a.scale * (ow[f][r] - dr[r] * op[f][r] + dqr[f][r]));
+                    }
             }
         }
         cc = cr;
@@ -952,6 +985,7 @@ struct RelGradArgs {
     float scale;
     const int32_t* seq_len;   // [B] tokens of every sequence, or null
     int32_t grad_bf16;        // dQ holds bf16 elements
+    const int32_t* delta;     // packed batch: delta[level][sequence] (only the token level is used here), or null
 };
 // tile slots per thread fetched one block ahead: 8 (512 threads: 16 chunks) with up to 256 ids, 24 with more --
 // those graphs have 25..30 slots per thread and block, and one workgroup per compute unit to hide their latency
@@ -961,7 +995,7 @@ struct RgPrefetch {
 };
 constexpr int kRgTileMaxIds = 512;
 // CPW: 16-id chunks per wavefront (2: up to 256 ids, 4: up to 512)
-template <int CPW>
+template <int CPW, bool PACKED = false>
 __global__ void __launch_bounds__(kThreads, CPW == 2 ? 4 : 2) rel_grad_tile_kernel(const RelGradArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int kRgPrefetch = RgPrefetch<CPW>::value;
@@ -1011,7 +1045,9 @@ __global__ void __launch_bounds__(kThreads, CPW == 2 ? 4 : 2) rel_grad_tile_kern
         qpiece = make_uint4(0u, 0u, 0u, 0u);
         if (threadIdx.x < kRgRows * 8) {
             const int r = threadIdx.x >> 3, c = (threadIdx.x & 7) * 8;
-            if (row0 + r < a.n) qpiece = *reinterpret_cast<const uint4*>(a.Q + base + (int64_t)(row0 + r) * a.sn + c);
+            // packed batch: the sequence's token rows begin at its delta of level 0; rows past its end are other nodes'
+            const int live = PACKED ? len : a.n, tok0 = PACKED ? a.delta[bh / a.H] : 0;
+            if (row0 + r < live) qpiece = *reinterpret_cast<const uint4*>(a.Q + base + (int64_t)(row0 + r + tok0) * a.sn + c);
         } else if (threadIdx.x < kRgRows * 8 + kRgRows) {
             const int r = threadIdx.x - kRgRows * 8;
             dl_own = row0 + r < a.n ? a.stat[(int64_t)bh * a.N + row0 + r].y : 0.f;
@@ -1074,10 +1110,11 @@ __global__ void __launch_bounds__(kThreads, CPW == 2 ? 4 : 2) rel_grad_tile_kern
         // the dQ values this thread will add to, and everything the next block needs
         const int mc = wave >> 2, fc = wave & 3;
         float dq_old[4];
+        const int live = PACKED ? seq_length_u(a.seq_len, bh / a.H, a.n) : a.n, tok0 = PACKED ? a.delta[bh / a.H] : 0;
 #pragma unroll
         for (int m = 0; m < 4; ++m) {
             const int row = row0 + 16 * mc + 4 * g + m;
-            dq_old[m] = row < a.n ? load_grad(a.dQ, base + (int64_t)row * a.sn + 16 * fc + j, a.grad_bf16) : 0.f;
+            dq_old[m] = row < live ? load_grad(a.dQ, base + (int64_t)(row + tok0) * a.sn + 16 * fc + j, a.grad_bf16) : 0.f;
         }
         const int blk_next = next_block(blk + gridDim.x);
         if (blk_next < total) prefetch(blk_next);
@@ -1092,7 +1129,7 @@ __global__ void __launch_bounds__(kThreads, CPW == 2 ? 4 : 2) rel_grad_tile_kern
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
                 const int row = row0 + 16 * mc + 4 * g + m;
-                if (row < a.n) store_grad(a.dQ, base + (int64_t)row * a.sn + 16 * fc + j, dq_old[m] + a.scale * dq[m], a.grad_bf16);
+                if (row < live) store_grad(a.dQ, base + (int64_t)(row + tok0) * a.sn + 16 * fc + j, dq_old[m] + a.scale * dq[m], a.grad_bf16);
             }
         }
         bf16x8_t qb[4];

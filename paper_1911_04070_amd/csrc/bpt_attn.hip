@@ -156,6 +156,9 @@ void fill_common(AttnArgs& a, const bpt_graph* g, const bpt_shape_t* s) {
     a.seq_len = s->seq_len;
     a.leave_unkept = s->seq_len && s->leave_unkept ? 1 : 0;
     a.grad_bf16 = s->grad_dtype == BPT_BF16 ? 1 : 0;
+    a.delta = nullptr;
+    a.lse_sb = (int64_t)s->H * g->num_nodes;
+    a.lse_sh = g->num_nodes;
     a.lg = g->num_levels - 1;
     const double p = s->dropout_p > 0.f ? (double)s->dropout_p : 0.0;
     a.drop_thr = p > 0.0 ? (uint32_t)std::min(std::floor(p * 4294967296.0), 4294967295.0) : 0u;
@@ -226,9 +229,13 @@ int run_bwd_q_tiles(const bpt_graph* g, const AttnArgs& a, const DeviceLimits& l
     if (dense) {   // no (w, p) pairs: the kernel leaves one copy of d_rel per workgroup
         t.drel_part = a.drel_part;
         const int grid = dense_grid(lim);
+        if (a.delta) return launch_tiles("bwd_q_tile_kernel", bwd_q_tile_kernel<true, false, true, true>, t, lim, tp.lds, st, grid);
         return a.drop_thr ? launch_tiles("bwd_q_tile_kernel", bwd_q_tile_kernel<true, true, true>, t, lim, tp.lds, st, grid)
                           : launch_tiles("bwd_q_tile_kernel", bwd_q_tile_kernel<true, false, true>, t, lim, tp.lds, st, grid);
     }
+    if (a.delta)   // a packed batch (no dropout there)
+        return tp.rel_lds ? launch_tiles("bwd_q_tile_kernel", bwd_q_tile_kernel<true, false, false, true>, t, lim, tp.lds, st)
+                          : launch_tiles("bwd_q_tile_kernel", bwd_q_tile_kernel<false, false, false, true>, t, lim, tp.lds, st);
     if (a.drop_thr)
         return tp.rel_lds ? launch_tiles("bwd_q_tile_kernel", bwd_q_tile_kernel<true, true>, t, lim, tp.lds, st)
                           : launch_tiles("bwd_q_tile_kernel", bwd_q_tile_kernel<false, true>, t, lim, tp.lds, st);
@@ -269,6 +276,11 @@ void fill_tile_args(TileArgs& t, const bpt_graph* g, const AttnArgs& a, const Ti
     t.seq_len = a.seq_len;
     t.leave_unkept = a.leave_unkept;
     t.grad_bf16 = a.grad_bf16;
+    t.delta = a.delta;
+    t.levels = g->num_levels;
+    t.lg = g->num_levels - 1;
+    t.lse_sb = a.lse_sb;
+    t.lse_sh = a.lse_sh;
     t.id_to_cid = g->tiles.id_to_cid;
     t.n = g->n;
     t.k = g->k;
@@ -318,6 +330,9 @@ void fill_span_args(SpanArgs& t, const bpt_graph* g, const AttnArgs& a) {
     t.seq_len = a.seq_len;
     t.leave_unkept = a.leave_unkept;
     t.grad_bf16 = a.grad_bf16;
+    t.delta = a.delta;
+    t.lse_sb = a.lse_sb;
+    t.lse_sh = a.lse_sh;
     t.drop_thr = a.drop_thr;
     t.drop_seed = a.drop_seed;
     t.drop_inv_keep = a.drop_inv_keep;
@@ -329,7 +344,13 @@ int run_span_tiles(const bpt_graph* g, const AttnArgs& a, bool forward, hipStrea
     const int64_t items = (int64_t)a.BH * (g->n / kSpanTok);
     const unsigned grid = (unsigned)((items + kTileWaves - 1) / kTileWaves);
     const size_t lds = (size_t)kTileWaves * kSpanTok * kVStride * sizeof(bf16_t);
-    if (forward && t.drop_thr)
+    if (t.delta && forward)
+        BPT_LAUNCH("fwd_span_tile_kernel", (fwd_span_tile_kernel<false, true>), dim3(grid), dim3(kTileThreads), lds, st, t);
+    else if (t.delta && t.grad_bf16)
+        BPT_LAUNCH("bwd_q_span_tile_kernel", (bwd_q_span_tile_kernel<false, true, true>), dim3(grid), dim3(kTileThreads), lds, st, t);
+    else if (t.delta)
+        BPT_LAUNCH("bwd_q_span_tile_kernel", (bwd_q_span_tile_kernel<false, false, true>), dim3(grid), dim3(kTileThreads), lds, st, t);
+    else if (forward && t.drop_thr)
         BPT_LAUNCH("fwd_span_tile_kernel", fwd_span_tile_kernel<true>, dim3(grid), dim3(kTileThreads), lds, st, t);
     else if (forward)
         BPT_LAUNCH("fwd_span_tile_kernel", fwd_span_tile_kernel<false>, dim3(grid), dim3(kTileThreads), lds, st, t);
@@ -351,11 +372,17 @@ int run_span_tiles(const bpt_graph* g, const AttnArgs& a, bool forward, hipStrea
         const int per_block = kSpanBigThreads / 64;   // short rows per workgroup
         const int small_blocks = (int)(((int64_t)a.BH * rows_small + per_block - 1) / per_block);
         const unsigned mgrid = (unsigned)(small_blocks + (int64_t)a.BH * rows_big);
-        if (forward)
-            BPT_LAUNCH("fwd_span_merge_kernel", fwd_span_merge_kernel, dim3(mgrid), dim3(kSpanBigThreads), 0, st, t, first,
+        if (forward && t.delta)
+            BPT_LAUNCH("fwd_span_merge_kernel", fwd_span_merge_kernel<true>, dim3(mgrid), dim3(kSpanBigThreads), 0, st, t, first,
+                       rows_small, first_big, rows_big, small_blocks);
+        else if (forward)
+            BPT_LAUNCH("fwd_span_merge_kernel", fwd_span_merge_kernel<false>, dim3(mgrid), dim3(kSpanBigThreads), 0, st, t, first,
+                       rows_small, first_big, rows_big, small_blocks);
+        else if (t.delta)
+            BPT_LAUNCH("bwd_q_span_merge_kernel", bwd_q_span_merge_kernel<true>, dim3(mgrid), dim3(kSpanBigThreads), 0, st, t, first,
                        rows_small, first_big, rows_big, small_blocks);
         else
-            BPT_LAUNCH("bwd_q_span_merge_kernel", bwd_q_span_merge_kernel, dim3(mgrid), dim3(kSpanBigThreads), 0, st, t, first,
+            BPT_LAUNCH("bwd_q_span_merge_kernel", bwd_q_span_merge_kernel<false>, dim3(mgrid), dim3(kSpanBigThreads), 0, st, t, first,
                        rows_small, first_big, rows_big, small_blocks);
         BPT_HIP(hipGetLastError());
     }
@@ -366,6 +393,9 @@ int run_span_tiles(const bpt_graph* g, const AttnArgs& a, bool forward, hipStrea
 int run_fwd_tiles(const bpt_graph* g, AttnArgs& a, const DeviceLimits& lim, const TilePlan& tp, hipStream_t st) {
     TileArgs t = {};
     fill_tile_args(t, g, a, tp);
+    if (a.delta)   // a packed batch (no dropout there)
+        return tp.rel_lds ? launch_tiles("fwd_tile_kernel", fwd_tile_kernel<true, false, true>, t, lim, tp.lds, st)
+                          : launch_tiles("fwd_tile_kernel", fwd_tile_kernel<false, false, true>, t, lim, tp.lds, st);
     if (a.drop_thr)
         return tp.rel_lds ? launch_tiles("fwd_tile_kernel", fwd_tile_kernel<true, true>, t, lim, tp.lds, st)
                           : launch_tiles("fwd_tile_kernel", fwd_tile_kernel<false, true>, t, lim, tp.lds, st);
@@ -574,13 +604,24 @@ int run_bwd_q(const bpt_graph* g, const BwdPlan& p, AttnArgs& a, hipStream_t st)
         t.scale = a.scale;
         t.seq_len = a.seq_len;
         t.grad_bf16 = a.grad_bf16;
+        t.delta = a.delta;
         if (p.dense_ds) {
             // bwd_q_tile_kernel has left the copies of d_rel
+        } else if (p.drel_part_rows <= 256 && t.delta) {
+            if (p.drel_lds > 65536)
+                BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rel_grad_tile_kernel<2, true>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.drel_lds));
+            BPT_LAUNCH("rel_grad_tile_kernel", (rel_grad_tile_kernel<2, true>), dim3(p.drel_grid_x), dim3(kThreads), p.drel_lds, st, t);
         } else if (p.drel_part_rows <= 256) {
             if (p.drel_lds > 65536)
                 BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rel_grad_tile_kernel<2>),
                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.drel_lds));
             BPT_LAUNCH("rel_grad_tile_kernel", rel_grad_tile_kernel<2>, dim3(p.drel_grid_x), dim3(kThreads), p.drel_lds, st, t);
+        } else if (t.delta) {
+            if (p.drel_lds > 65536)
+                BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rel_grad_tile_kernel<4, true>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.drel_lds));
+            BPT_LAUNCH("rel_grad_tile_kernel", (rel_grad_tile_kernel<4, true>), dim3(p.drel_grid_x), dim3(kThreads), p.drel_lds, st, t);
         } else {
             if (p.drel_lds > 65536)
                 BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rel_grad_tile_kernel<4>),
@@ -608,34 +649,37 @@ int run_bwd_q(const bpt_graph* g, const BwdPlan& p, AttnArgs& a, hipStream_t st)
     return BPT_OK;
 }
 
-template <int NBC, bool DROP>
+template <int NBC, bool DROP, bool PACKED = false>
 int launch_kv_tiles_as(const KeyArgs& t, const BwdPlan& p, const DeviceLimits& lim, hipStream_t st) {
     if (p.kv_lds > 65536)
-        BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_kv_tile_kernel<NBC, DROP>),
+        BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_kv_tile_kernel<NBC, DROP, PACKED>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.kv_lds));
     const int grid =
-        std::max(8, lim.cus * resident_blocks(bwd_kv_tile_kernel<NBC, DROP>, kTileThreads, p.kv_lds, lim) / 8 * 8);
-    BPT_LAUNCH("bwd_kv_tile_kernel", (bwd_kv_tile_kernel<NBC, DROP>), dim3(grid), dim3(kTileThreads), p.kv_lds, st, t);
+        std::max(8, lim.cus * resident_blocks(bwd_kv_tile_kernel<NBC, DROP, PACKED>, kTileThreads, p.kv_lds, lim) / 8 * 8);
+    BPT_LAUNCH("bwd_kv_tile_kernel", (bwd_kv_tile_kernel<NBC, DROP, PACKED>), dim3(grid), dim3(kTileThreads), p.kv_lds, st, t);
     BPT_HIP(hipGetLastError());
     return BPT_OK;
 }
 template <int NBC>
 int launch_kv_tiles(const KeyArgs& t, const BwdPlan& p, const DeviceLimits& lim, hipStream_t st) {
+    if (t.delta) return launch_kv_tiles_as<NBC, false, true>(t, p, lim, st);   // a packed batch (no dropout there)
     return t.drop_thr ? launch_kv_tiles_as<NBC, true>(t, p, lim, st) : launch_kv_tiles_as<NBC, false>(t, p, lim, st);
 }
-template <int NBC, bool DROP, bool G16>
+template <int NBC, bool DROP, bool G16, bool PACKED = false>
 int launch_kv_chain_as(const KeyArgs& t, const BwdPlan& p, const DeviceLimits& lim, hipStream_t st) {
     if (p.kv_lds > 65536)
-        BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_kv_chain_kernel<NBC, DROP, G16>),
+        BPT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_kv_chain_kernel<NBC, DROP, G16, PACKED>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.kv_lds));
     const int grid =
-        std::max(8, lim.cus * resident_blocks(bwd_kv_chain_kernel<NBC, DROP, G16>, kTileThreads, p.kv_lds, lim) / 8 * 8);
-    BPT_LAUNCH("bwd_kv_chain_kernel", (bwd_kv_chain_kernel<NBC, DROP, G16>), dim3(grid), dim3(kTileThreads), p.kv_lds, st, t);
+        std::max(8, lim.cus * resident_blocks(bwd_kv_chain_kernel<NBC, DROP, G16, PACKED>, kTileThreads, p.kv_lds, lim) / 8 * 8);
+    BPT_LAUNCH("bwd_kv_chain_kernel", (bwd_kv_chain_kernel<NBC, DROP, G16, PACKED>), dim3(grid), dim3(kTileThreads), p.kv_lds, st, t);
     BPT_HIP(hipGetLastError());
     return BPT_OK;
 }
 template <int NBC>
 int launch_kv_chain(const KeyArgs& t, const BwdPlan& p, const DeviceLimits& lim, hipStream_t st) {
+    if (t.delta)   // a packed batch (no dropout there)
+        return t.grad_bf16 ? launch_kv_chain_as<NBC, false, true, true>(t, p, lim, st) : launch_kv_chain_as<NBC, false, false, true>(t, p, lim, st);
     if (t.grad_bf16)
         return t.drop_thr ? launch_kv_chain_as<NBC, true, true>(t, p, lim, st) : launch_kv_chain_as<NBC, false, true>(t, p, lim, st);
     return t.drop_thr ? launch_kv_chain_as<NBC, true, false>(t, p, lim, st) : launch_kv_chain_as<NBC, false, false>(t, p, lim, st);
@@ -685,6 +729,7 @@ int run_bwd_kv_tiles(const bpt_graph* g, const BwdPlan& p, const AttnArgs& a, co
     t.seq_len = a.seq_len;
     t.leave_unkept = a.leave_unkept;
     t.grad_bf16 = a.grad_bf16;
+    t.delta = a.delta;
     t.n = g->n;
     t.drop_thr = a.drop_thr;
     t.drop_seed = a.drop_seed;
@@ -715,8 +760,12 @@ int run_bwd_kv_tiles(const bpt_graph* g, const BwdPlan& p, const AttnArgs& a, co
     const int64_t zero_elems = (int64_t)a.BH * ((a.N - zero_row0 + 63) / 64) * 64;
     const int64_t blocks = (int64_t)a.BH * kt.num_multi + (zero_elems + 255) / 256;
     if (blocks > 0) {
-        BPT_LAUNCH("kv_tile_merge_kernel", kv_tile_merge_kernel, dim3((unsigned)blocks), dim3(256), 0, st, t, kt.multi_tile,
-                   kt.multi_ptr, kt.num_multi, kt.first_uncovered);
+        if (t.delta)
+            BPT_LAUNCH("kv_tile_merge_kernel", kv_tile_merge_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, st, t, kt.multi_tile,
+                       kt.multi_ptr, kt.num_multi, kt.first_uncovered);
+        else
+            BPT_LAUNCH("kv_tile_merge_kernel", kv_tile_merge_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, st, t, kt.multi_tile,
+                       kt.multi_ptr, kt.num_multi, kt.first_uncovered);
         BPT_HIP(hipGetLastError());
     }
     return BPT_OK;
@@ -754,6 +803,41 @@ int run_bwd_kv(const bpt_graph* g, const BwdPlan& p, AttnArgs& a, bool queue_cle
     return BPT_OK;
 }
 
+// A batch graph on the matrix-core kernels.  The kernels walk the tree of one sequence (g->tree: ids, tile
+// metadata) once per sequence and head, with the lengths the graph was built for and with the rows of nodes that a
+// sequence does not keep neither computed nor written -- exactly a call with seq_len and leave_unkept on the padded
+// trees -- and move every row of a caller's tensor by the sequence's delta of the node's level (AttnArgs.delta).
+// Applies to bf16 tensors with B = 1 when the tree has token tiles and span blocks; *view is then the shape the
+// kernels see: one batch entry per sequence, all at the same base address.
+bool packed_tiles(const bpt_graph* g, const bpt_shape_t* s, bpt_shape_t* view) {
+    if (g->batch <= 0 || !g->tree || !g->d_delta || !g->d_lengths || s->dtype != BPT_BF16 || s->B != 1) return false;
+    *view = *s;
+    view->B = g->batch;
+    view->stride_b = 0;
+    view->seq_len = g->d_lengths;
+    view->leave_unkept = 1;
+    if (check_shape(g->tree, view) != BPT_OK) return false;
+    DeviceLimits lim;
+    if (device_limits(g->tree, &lim) != BPT_OK) return false;
+    return plan_tiles(g->tree, lim).ok && span_tiles_ok(g->tree);
+}
+// the arguments of such a call: those of the view on the tree, with the extent of the packed tensors and their rows
+void fill_packed(AttnArgs& a, const bpt_graph* g, const bpt_shape_t* s, const bpt_shape_t* view) {
+    fill_common(a, g->tree, view);
+    const int64_t es = 2;
+    a.slab_bytes = (uint32_t)(((int64_t)(g->num_nodes - 1) * s->stride_n + kD) * es);
+    a.delta = g->d_delta;
+    a.lse_sb = 0;
+    a.lse_sh = g->num_nodes;
+}
+
+// the same for the backward: all three of its tile kernels have to apply to the tree
+bool packed_tiles_bwd(const bpt_graph* g, const bpt_shape_t* s, bpt_shape_t* view) {
+    if (!packed_tiles(g, s, view)) return false;
+    BwdPlan p;
+    return plan_bwd(g->tree, view, &p) == BPT_OK && p.q_tiles && p.kv_tiles;
+}
+
 enum { kStageQ = 1, kStageKV = 2 };
 
 int backward(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q, const void* K, const void* V, const void* rel,
@@ -767,12 +851,21 @@ int backward(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q, const vo
     if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(rel) || misaligned(dout) || misaligned(dQ) ||
         misaligned(dK) || misaligned(dV) || misaligned(d_rel) || misaligned(workspace))
         return BPT_ERR_INVALID_ARG;
+    // a batch graph on the matrix-core kernels: from here on g and s are the tree of one sequence and the view of
+    // the packed tensors as one batch entry per sequence
+    bpt_shape_t view;
+    AttnArgs a;
+    if (packed_tiles_bwd(g, s, &view)) {
+        fill_packed(a, g, s, &view);
+        g = g->tree;
+        s = &view;
+    } else {
+        fill_common(a, g, s);
+    }
     BwdPlan p;
     if ((rc = plan_bwd(g, s, &p))) return rc;
     if (!workspace || workspace_bytes < p.total) return BPT_ERR_INVALID_ARG;
     unsigned char* ws = static_cast<unsigned char*>(workspace);
-    AttnArgs a;
-    fill_common(a, g, s);
     a.Q = Q;
     a.K = K;
     a.V = V;
@@ -809,6 +902,8 @@ extern "C" {
 
 size_t bpt_attn_fwd_workspace(const bpt_graph_t* g, const bpt_shape_t* s) {
     if (bpt::check_shape(g, s) != BPT_OK) return SIZE_MAX;
+    bpt_shape_t view;
+    if (bpt::packed_tiles(g, s, &view)) return bpt_attn_fwd_workspace(g->tree, &view);
     return bpt::align_up((size_t)s->B * s->H *
                          std::max<size_t>(std::max(g->fwd.num_part, g->fwd_span.num_part), bpt::span_partials(g)) *
                          bpt::kPartStride * sizeof(float));
@@ -816,6 +911,8 @@ size_t bpt_attn_fwd_workspace(const bpt_graph_t* g, const bpt_shape_t* s) {
 
 size_t bpt_attn_bwd_workspace(const bpt_graph_t* g, const bpt_shape_t* s) {
     if (bpt::check_shape(g, s) != BPT_OK) return SIZE_MAX;
+    bpt_shape_t view;
+    if (bpt::packed_tiles_bwd(g, s, &view)) return bpt_attn_bwd_workspace(g->tree, &view);
     bpt::BwdPlan p;
     if (bpt::plan_bwd(g, s, &p) != BPT_OK) return SIZE_MAX;
     return p.total;
@@ -833,7 +930,14 @@ int bpt_attn_fwd(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q, cons
     if (need == SIZE_MAX) return BPT_ERR_UNSUPPORTED;
     if (need > 0 && (!workspace || workspace_bytes < need)) return BPT_ERR_INVALID_ARG;
     bpt::AttnArgs a;
-    bpt::fill_common(a, g, s);
+    bpt_shape_t view;
+    const bool packed = bpt::packed_tiles(g, s, &view);
+    if (packed) {
+        bpt::fill_packed(a, g, s, &view);
+        g = g->tree;
+    } else {
+        bpt::fill_common(a, g, s);
+    }
     a.Q = Q;
     a.K = K;
     a.V = V;

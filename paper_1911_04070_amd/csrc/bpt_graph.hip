@@ -942,7 +942,18 @@ int build_batch(int32_t n, int32_t k, int32_t causal, const int32_t* lengths, in
     BPT_HIP(hipMemcpyAsync(h_tptr.data(), g->t_ptr, sizeof(int32_t) * h_tptr.size(), hipMemcpyDeviceToHost, st));
     BPT_HIP(hipStreamSynchronize(st));
     if ((rc = make_schedule(h_ptr, 0, T, g->fwd))) return rc;
-    return make_schedule(h_tptr, 0, num_nodes, g->tr);
+    if ((rc = make_schedule(h_tptr, 0, num_nodes, g->tr))) return rc;
+
+    // 6. for the matrix-core kernels: the tree of one sequence with its tile metadata, the lengths and the row deltas
+    g->tree = new (std::nothrow) bpt_graph();
+    if (!g->tree) return BPT_ERR_ALLOC;
+    if ((rc = build(n, k, causal, st, g->tree))) return rc;
+    std::vector<int32_t> h_delta((size_t)num_levels * B);
+    for (int l = 0; l < num_levels; ++l)
+        for (int b = 0; b < B; ++b) h_delta[(size_t)l * B + b] = g->first_row[(size_t)l * B + b] - (int32_t)level_offset(n, l);
+    std::vector<int32_t> h_len(lengths, lengths + B);
+    if ((rc = upload(h_delta, &g->d_delta)) || (rc = upload(h_len, &g->d_lengths))) return rc;
+    return BPT_OK;
 }
 
 }  // namespace
@@ -1091,6 +1102,9 @@ void bpt_graph_destroy(bpt_graph_t* g) {
     bpt::free_schedule(g->fwd_span);
     bpt::free_tiles(g->tiles);
     bpt::free_key_tiles(g->ktiles);
+    (void)hipFree(g->d_lengths);
+    (void)hipFree(g->d_delta);
+    bpt_graph_destroy(g->tree);
     delete g;
 }
 

@@ -86,6 +86,10 @@ struct bpt_graph {
     int32_t n_tokens = 0;         // token rows (they come first): n, or the tokens of all sequences of a batch graph
     int32_t batch = 0;            // sequences packed into this graph (bpt_build_batch_graph); 0: the graph of one sequence
     std::vector<int32_t> first_row, row_count;   // batch graph: [level][sequence] first node row and node count
+    // batch graph, for the matrix-core kernels: the graph of one sequence of n tokens (their tile metadata), and on the
+    // device the lengths [sequence] and delta[level][sequence] = first_row - first id of the level in that tree
+    bpt_graph* tree = nullptr;
+    int32_t *d_lengths = nullptr, *d_delta = nullptr;
     int64_t num_edges = 0;
     int64_t num_token_edges = 0;  // edges of token rows: they come first in the CSR
     int device = 0;
