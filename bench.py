@@ -230,20 +230,22 @@ def bench_layer(args, w, bpt, torch, np):
     bf16 weights."""
     from paper_1911_04070_amd.workloads import make_lengths
     d, d_ff = w.H * w.D, 4 * w.H * w.D
-    g = bpt.bpt_build_graph(w.n, w.k, w.causal)
+    packed = args.packed and bool(w.length_mix)   # one graph for the batch, rows of kept nodes only: X is [1][rows][d]
+    g = bpt.bpt_build_batch_graph(w.n, w.k, w.causal, make_lengths(w)) if packed else bpt.bpt_build_graph(w.n, w.k, w.causal)
+    B = 1 if packed else w.B
     gen = torch.Generator(device="cuda").manual_seed(1911 + w.index)
     rnd = lambda *shape, s=1.0: (s * torch.randn(*shape, device="cuda", generator=gen))
-    X = rnd(w.B, g.num_nodes, d).to(torch.bfloat16)
-    X[:, w.n:] = 0                                            # span nodes start from zero
+    X = rnd(B, g.num_nodes, d).to(torch.bfloat16)
+    X[:, g.n_tokens:] = 0                                     # span nodes start from zero
     R = rnd(g.num_levels, g.rel_width, w.D, s=0.02).to(torch.bfloat16)
     p = layer_params(torch, rnd, d, d_ff)
-    lens_d = torch.from_numpy(make_lengths(w)).cuda() if w.length_mix else None
+    lens_d = torch.from_numpy(make_lengths(w)).cuda() if w.length_mix and not packed else None
     Y = torch.empty_like(X)
-    dY = rnd(w.B, g.num_nodes, d).to(torch.bfloat16)
+    dY = rnd(B, g.num_nodes, d).to(torch.bfloat16)
     dX = torch.empty_like(X)
     d_rel = torch.empty(R.shape, dtype=torch.float32, device="cuda")
     grads = {"d" + k_: torch.empty(v.shape, dtype=torch.float32, device="cuda") for k_, v in p.items()}
-    fws, bws = bpt.layer_workspace_bytes(g, w.B, w.H, d_ff)
+    fws, bws = bpt.layer_workspace_bytes(g, B, w.H, d_ff)
     ws = torch.empty(fws + 256, dtype=torch.uint8, device="cuda")
     ws_b = torch.empty(bws + 256, dtype=torch.uint8, device="cuda")
     fwd = lambda: bpt.bpt_layer_fwd(g, X, R, p, w.H, scale=w.scale, seq_len=lens_d, out=Y, workspace=ws)
@@ -272,14 +274,14 @@ def bench_layer(args, w, bpt, torch, np):
     torch.cuda.synchronize()
     own = {name: total / 5 for name, (calls, total) in bpt.bpt_profile_report().items()}   # ms per step, all its launches
     bpt.bpt_profile_enable(False)
-    rows = w.B * g.num_nodes
+    rows = B * g.num_nodes
     flops = 3 * 2.0 * rows * (4 * d * d + 2 * d * d_ff)       # the backward has two products per forward product
     print(json.dumps({
         "metric": "BPT graph layer fwd+bwd node rows/sec", "value": round(rows / (ms * 1e-3), 1), "unit": "rows/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
         "dtype": "bf16", "data": "synthetic", "vs_baseline": None, "forward_ms": round(ms_fwd, 4),
-        "config": {"workload": w.name + "+layer", "n": w.n, "k": w.k, "causal": w.causal, "batch": w.B, "heads": w.H,
-                   "d_model": d, "d_ff": d_ff, "node_rows": rows},
+        "config": {"workload": w.name + "+layer" + ("+packed" if packed else ""), "n": w.n, "k": w.k, "causal": w.causal, "batch": w.B,
+                   "heads": w.H, "d_model": d, "d_ff": d_ff, "node_rows": rows, "workspace_MB": round((fws + bws) / 1e6, 1)},
         "dense_TFLOPs": round(flops / (ms * 1e-3) / 1e12, 1),
         "own_kernel_ms": {k_: round(v, 4) for k_, v in sorted(own.items(), key=lambda kv: -kv[1])},
         "gemm_and_gaps_ms": round(ms - sum(own.values()), 4),

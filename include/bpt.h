@@ -124,8 +124,10 @@ int bpt_build_graph(int32_t n, int32_t k, int32_t causal, void* stream, bpt_grap
  * the relative-position table is shared by all sequences (Sec. 3.4).
  * The attention calls (and bpt_layer_fwd / bpt_layer_bwd) take such a graph like any other,
  * with N = its row count, B = 1 (or B independent batches of the same length mix) and
- * seq_len = NULL (BPT_ERR_INVALID_ARG otherwise); they run the library's gather kernels on
- * it (the dense-tile kernels are built for the tree of one sequence).  Dropout on the
+ * seq_len = NULL (BPT_ERR_INVALID_ARG otherwise).  bf16 tensors with B = 1 run the matrix-core
+ * kernels (they walk the tree of one sequence once per sequence and head and address the packed
+ * rows through the per-level offsets; n >= 32 and at most 512 relative-position ids in use),
+ * anything else the gather kernels; the results are the same rows either way.  Dropout on the
  * attention weights and the bpt_stack_* calls are refused on it (BPT_ERR_UNSUPPORTED).
  * More than 2^23 rows: BPT_ERR_UNSUPPORTED.  Synchronises `stream`. */
 int bpt_build_batch_graph(int32_t n, int32_t k, int32_t causal, const int32_t* lengths, int32_t batch,

@@ -149,6 +149,49 @@ def test_layer_backward(n, k, causal, B, heads, d_ff, lengths, decisive):
     g.destroy()
 
 
+@pytest.mark.parametrize("n,k,causal,heads,d_ff,lengths", [
+    (256, 3, False, 4, 512, [256, 150, 31, 1]), (512, 4, True, 2, 256, [77, 512, 300]),
+])
+def test_layer_on_the_graph_of_a_packed_batch(n, k, causal, heads, d_ff, lengths):
+    # one graph for the batch, rows only for the nodes that exist (bpt_build_batch_graph): X, Y, dY, dX are
+    # [1][rows][d]; the oracle runs the padded trees with the lengths and is read at the kept rows
+    print("layer on a packed batch", n, k, causal, heads, d_ff, lengths, flush=True)
+    B = len(lengths)
+    X, Rel, p = make_case(n, k, causal, B, heads, d_ff, 500 + n + heads, False)
+    p["b1"] = np.where(np.arange(d_ff) % 2 == 0, 6.0, -6.0).astype(np.float32)
+    rng = np.random.Generator(np.random.PCG64(78 + n))
+    dY = round_to_bf16(rng.standard_normal(X.shape).astype(np.float32))[0]
+    _, b_of, node_of = oracle.batch_rows(n, lengths)
+    g = bpt.bpt_build_batch_graph(n, k, causal, lengths)
+    assert g.num_nodes == len(b_of)
+    Xp = torch.from_numpy(X[b_of, node_of][None]).to(torch.bfloat16).cuda().contiguous()
+    dYp = torch.from_numpy(dY[b_of, node_of][None]).to(torch.bfloat16).cuda().contiguous()
+    Rd, pd = torch.from_numpy(Rel).to(torch.bfloat16).cuda(), to_dev(p)
+    fws, bws = bpt.layer_workspace_bytes(g, 1, heads, d_ff)
+    ws_f = torch.empty(fws + 256, dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(bws + 256, dtype=torch.uint8, device="cuda")
+    Y = bpt.bpt_layer_fwd(g, Xp, Rd, pd, heads, scale=0.125, workspace=ws_f)
+    dX, d_rel, grads = bpt.bpt_layer_bwd(g, Xp, Rd, pd, heads, ws_f, dYp, scale=0.125, workspace=ws_b)
+    torch.cuda.synchronize()
+    ref_y = layer_forward(n, k, causal, heads, X, Rel, p, 0.125, lengths=lengths)
+    err = float(np.abs(Y.float().cpu().numpy()[0].astype(np.float64) - ref_y[b_of, node_of]).max())
+    print("   forward max-abs error %.3g" % err, flush=True)
+    assert err <= TOL, err
+    ref = layer_backward(n, k, causal, heads, X, Rel, p, dY, 0.125, lengths=lengths)
+    ref["dX"] = ref["dX"][b_of, node_of][None]
+    got = {"dX": dX, "dRel": d_rel}
+    got.update(grads)
+    worst = {}
+    for name in ("dX", "dRel") + GRADS:
+        a = got[name].float().cpu().numpy().astype(np.float64)
+        assert np.isfinite(a).all() and a.shape == ref[name].shape, name
+        worst[name] = float(np.abs(a - ref[name]).max()) / max(float(np.abs(ref[name]).max()), 1e-30)
+    print("   relative max-abs errors", {k_: float("%.2g" % v) for k_, v in worst.items()}, flush=True)
+    for name, v in worst.items():
+        assert v <= BWD_TOL_DECISIVE, (name, v)
+    g.destroy()
+
+
 def test_misaligned_tensors_are_refused():
     # the kernels move 16 bytes per lane: a tensor that starts 2 bytes off is an error, not a fault
     n, k, B, heads, d_ff = 64, 2, 1, 1, 64
