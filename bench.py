@@ -112,17 +112,19 @@ def bench_stack(args, w, bpt, torch, np):
     (classification) of the last layer and back; d = heads * 64, d_ff = 4 d, random bf16 weights."""
     from paper_1911_04070_amd.workloads import make_lengths
     d, d_ff, layers = w.H * w.D, 4 * w.H * w.D, args.layers
-    g = bpt.bpt_build_graph(w.n, w.k, w.causal)
+    packed = args.packed and bool(w.length_mix)   # one graph for the batch: E is [1][tokens of all sequences][d]
+    g = bpt.bpt_build_batch_graph(w.n, w.k, w.causal, make_lengths(w)) if packed else bpt.bpt_build_graph(w.n, w.k, w.causal)
+    B = 1 if packed else w.B
     gen = torch.Generator(device="cuda").manual_seed(1911 + w.index)
     rnd = lambda *shape, s=1.0: (s * torch.randn(*shape, device="cuda", generator=gen))
-    E = rnd(w.B, w.n, d).to(torch.bfloat16)
+    E = rnd(B, g.n_tokens, d).to(torch.bfloat16)
     rels = [rnd(g.num_levels, g.rel_width, w.D, s=0.02).to(torch.bfloat16) for _ in range(layers)]
     params = [layer_params(torch, rnd, d, d_ff) for _ in range(layers)]
-    lens_d = torch.from_numpy(make_lengths(w)).cuda() if w.length_mix else None
+    lens_d = torch.from_numpy(make_lengths(w)).cuda() if w.length_mix and not packed else None
     tokens_out = bool(w.causal)
     d_root = None if tokens_out else rnd(w.B, d).to(torch.bfloat16)
-    d_tokens = rnd(w.B, w.n, d).to(torch.bfloat16) if tokens_out else None
-    fws, bws = bpt.stack_workspace_bytes(g, w.B, w.H, d_ff, layers)
+    d_tokens = rnd(B, g.n_tokens, d).to(torch.bfloat16) if tokens_out else None
+    fws, bws = bpt.stack_workspace_bytes(g, B, w.H, d_ff, layers)
     ws = torch.empty(fws + 256, dtype=torch.uint8, device="cuda")
     ws_b = torch.empty(bws + 256, dtype=torch.uint8, device="cuda")
     fwd = lambda: bpt.bpt_stack_fwd(g, E, rels, params, w.H, scale=w.scale, seq_len=lens_d, want_root=not tokens_out,
@@ -143,14 +145,14 @@ def bench_stack(args, w, bpt, torch, np):
         bwd()
     ms = wall_ms(lambda: (fwd(), bwd()))
     ms_fwd = wall_ms(fwd)
-    rows = w.B * g.num_nodes
+    rows = B * g.num_nodes
     tokens = int(make_lengths(w).sum()) if w.length_mix else w.B * w.n   # the tokens that exist, not the padding
     flops = layers * 3 * 2.0 * rows * (4 * d * d + 2 * d * d_ff)
     print(json.dumps({
         "metric": "BPT graph update fwd+bwd tokens/sec", "value": round(tokens / (ms * 1e-3), 1), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
         "dtype": "bf16", "data": "synthetic", "vs_baseline": None, "forward_ms": round(ms_fwd, 4),
-        "config": {"workload": "%s+%d layers" % (w.name, layers), "n": w.n, "k": w.k, "causal": w.causal, "batch": w.B,
+        "config": {"workload": "%s+%d layers%s" % (w.name, layers, "+packed" if packed else ""), "n": w.n, "k": w.k, "causal": w.causal, "batch": w.B,
                    "heads": w.H, "d_model": d, "d_ff": d_ff, "layers": layers, "node_rows": rows, "tokens": tokens,
                    "output": "tokens" if tokens_out else "root"},
         "dense_TFLOPs": round(flops / (ms * 1e-3) / 1e12, 1),

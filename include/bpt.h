@@ -128,7 +128,7 @@ int bpt_build_graph(int32_t n, int32_t k, int32_t causal, void* stream, bpt_grap
  * kernels (they walk the tree of one sequence once per sequence and head and address the packed
  * rows through the per-level offsets; n >= 32 and at most 512 relative-position ids in use),
  * anything else the gather kernels; the results are the same rows either way.  Dropout on the
- * attention weights and the bpt_stack_* calls are refused on it (BPT_ERR_UNSUPPORTED).
+ * attention weights is refused on it (BPT_ERR_UNSUPPORTED).
  * More than 2^23 rows: BPT_ERR_UNSUPPORTED.  Synchronises `stream`. */
 int bpt_build_batch_graph(int32_t n, int32_t k, int32_t causal, const int32_t* lengths, int32_t batch,
                           void* stream, bpt_graph_t** out);
@@ -332,7 +332,11 @@ int bpt_layer_bwd(const bpt_graph_t* g, int32_t B, int32_t H, float scale, const
  * sequence's end hold unspecified values.  The workspace (bpt_stack_fwd_workspace bytes of
  * device memory) keeps every layer's input states and activations for bpt_stack_bwd; nothing
  * is allocated beyond what bpt_layer_fwd states, so after one call outside a capture the call
- * (and bpt_stack_bwd) can be captured into a HIP graph.  num_layers <= 256. */
+ * (and bpt_stack_bwd) can be captured into a HIP graph.  num_layers <= 256.
+ * On the graph of a packed batch (bpt_build_batch_graph): B = 1 and seq_len = NULL
+ * (BPT_ERR_INVALID_ARG otherwise), E and tokens are [T][d] with T = the tokens of all sequences in
+ * row order, and root is [batch][d], one row per sequence (zero for a sequence without tokens);
+ * bpt_stack_bwd takes d_root [batch][d] and d_tokens [T][d] and writes dE [T][d]. */
 size_t bpt_stack_fwd_workspace(const bpt_graph_t* g, int32_t B, int32_t H, int32_t d_ff, int32_t num_layers);
 int bpt_stack_fwd(const bpt_graph_t* g, int32_t B, int32_t H, int32_t num_layers, float scale, const int32_t* seq_len,
                   const void* const* rel, const void* E, const bpt_layer_params_t* p, void* root, void* tokens,

@@ -153,6 +153,7 @@ class Graph:
     def __init__(self, n: int, k: int, causal: bool, lengths=None):
         L = load_library()
         handle = ctypes.c_void_p()
+        self.is_batch = lengths is not None
         if lengths is None:
             _check(L.bpt_build_graph(int(n), int(k), int(bool(causal)), _stream_ptr(), ctypes.byref(handle)),
                    "bpt_build_graph(n=%d, k=%d, causal=%d)" % (n, k, causal))
@@ -534,8 +535,10 @@ def _stack_args(g: Graph, E: torch.Tensor, rels, params, heads: int, eps: float,
     """Checks the tensors of a stack call; returns (d_ff, array of parameter structs, array of rel pointers, the
     seq_len pointer)."""
     d = heads * 64
-    if E.dtype != torch.bfloat16 or E.dim() != 3 or E.shape[1] != g.n or E.shape[2] != d or not E.is_contiguous():
-        raise ValueError("E must be a contiguous bf16 [B, %d, %d] tensor" % (g.n, d))
+    if E.dtype != torch.bfloat16 or E.dim() != 3 or E.shape[1] != g.n_tokens or E.shape[2] != d or not E.is_contiguous():
+        raise ValueError("E must be a contiguous bf16 [B, %d, %d] tensor" % (g.n_tokens, d))
+    if g.is_batch and (E.shape[0] != 1 or seq_len is not None):
+        raise ValueError("the graph of a packed batch takes E [1, tokens of all sequences, d] and no seq_len")
     if len(params) < 1 or len(rels) != len(params):
         raise ValueError("one parameter dict and one rel table per layer")
     structs, lens, d_ff = [], None, None
@@ -560,7 +563,8 @@ def bpt_stack_fwd(g: Graph, E: torch.Tensor, rels, params, heads: int, scale: Op
                   seq_len: Optional[torch.Tensor] = None, want_root: bool = True, want_tokens: bool = True,
                   workspace: Optional[torch.Tensor] = None):
     """The update of the graph (Sec. 3.3) over len(params) layers: E [B, n, heads*64] bf16 token embeddings ->
-    (root [B, d] or None, tokens [B, n, d] or None).  rels: one [levels, rel_width, 64] bf16 table per layer;
+    (root [B, d] or None, tokens [B, n, d] or None); on the graph of a packed batch E and tokens are [1, T, d] (the tokens
+    of all sequences in row order) and root is [sequences, d].  rels: one [levels, rel_width, 64] bf16 table per layer;
     params: one dict per layer as for bpt_layer_fwd.  Pass a `workspace` (stack_workspace_bytes) to keep the
     activations for bpt_stack_bwd."""
     L = load_library()
@@ -568,7 +572,8 @@ def bpt_stack_fwd(g: Graph, E: torch.Tensor, rels, params, heads: int, scale: Op
     if not (want_root or want_tokens):
         raise ValueError("ask for the root, the tokens or both")
     B, d = E.shape[0], heads * 64
-    root = torch.empty((B, d), dtype=E.dtype, device=E.device) if want_root else None
+    roots = g.batch if g.is_batch else B      # one root per sequence
+    root = torch.empty((roots, d), dtype=E.dtype, device=E.device) if want_root else None
     tokens = torch.empty_like(E) if want_tokens else None
     need = _need(int(L.bpt_stack_fwd_workspace(g.handle, B, heads, d_ff, len(params))), "bpt_stack_fwd_workspace")
     if workspace is None:
@@ -588,7 +593,7 @@ def bpt_stack_bwd(g: Graph, E: torch.Tensor, rels, params, heads: int, fwd_works
     L = load_library()
     d_ff, lps, relp, lens = _stack_args(g, E, rels, params, heads, eps, seq_len)
     B, d = E.shape[0], heads * 64
-    for name, t, shape in (("d_root", d_root, (B, d)), ("d_tokens", d_tokens, tuple(E.shape))):
+    for name, t, shape in (("d_root", d_root, (g.batch if g.is_batch else B, d)), ("d_tokens", d_tokens, tuple(E.shape))):
         if t is not None and (t.dtype != torch.bfloat16 or tuple(t.shape) != shape or not t.is_contiguous()
                               or t.device != E.device):
             raise ValueError("%s must be a contiguous bf16 tensor of shape %s on the device of E" % (name, shape))

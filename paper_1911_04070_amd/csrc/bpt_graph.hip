@@ -953,6 +953,15 @@ int build_batch(int32_t n, int32_t k, int32_t causal, const int32_t* lengths, in
         for (int b = 0; b < B; ++b) h_delta[(size_t)l * B + b] = g->first_row[(size_t)l * B + b] - (int32_t)level_offset(n, l);
     std::vector<int32_t> h_len(lengths, lengths + B);
     if ((rc = upload(h_delta, &g->d_delta)) || (rc = upload(h_len, &g->d_lengths))) return rc;
+    // the roots (the last level keeps one node of every sequence that has a token)
+    std::vector<int32_t> h_root_row((size_t)B), h_root_seq;
+    const size_t top = (size_t)(num_levels - 1) * B;
+    g->first_root = g->first_row[top];
+    for (int b = 0; b < B; ++b) {
+        h_root_row[b] = g->row_count[top + b] > 0 ? g->first_row[top + b] : -1;
+        if (g->row_count[top + b] > 0) h_root_seq.push_back(b);
+    }
+    if ((rc = upload(h_root_row, &g->d_root_row)) || (rc = upload(h_root_seq, &g->d_root_seq))) return rc;
     return BPT_OK;
 }
 
@@ -1104,6 +1113,8 @@ void bpt_graph_destroy(bpt_graph_t* g) {
     bpt::free_key_tiles(g->ktiles);
     (void)hipFree(g->d_lengths);
     (void)hipFree(g->d_delta);
+    (void)hipFree(g->d_root_row);
+    (void)hipFree(g->d_root_seq);
     bpt_graph_destroy(g->tree);
     delete g;
 }

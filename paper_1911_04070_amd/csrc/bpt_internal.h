@@ -90,6 +90,10 @@ struct bpt_graph {
     // device the lengths [sequence] and delta[level][sequence] = first_row - first id of the level in that tree
     bpt_graph* tree = nullptr;
     int32_t *d_lengths = nullptr, *d_delta = nullptr;
+    // batch graph, for the stack's readout: the row of every sequence's root (-1: the sequence is empty), and for
+    // the rows from first_root on (the root level) the sequence they belong to
+    int32_t *d_root_row = nullptr, *d_root_seq = nullptr;
+    int32_t first_root = 0;
     int64_t num_edges = 0;
     int64_t num_token_edges = 0;  // edges of token rows: they come first in the CSR
     int device = 0;

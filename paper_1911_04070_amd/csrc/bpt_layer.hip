@@ -371,25 +371,33 @@ __global__ void __launch_bounds__(256) initial_states_kernel(const bf16_t* __res
     *reinterpret_cast<uint4*>(h + i * 8) = x;
 }
 
-// Sec. 3.3, the output: the root's row and / or the token rows of h [B][N][d], to root [B][d] and tokens
-// [B][n][d] (either may be null).  One thread per 8 values of the rows that are read.
+// Sec. 3.3, the output: the roots' rows and / or the token rows of h [B][N][d], to root [B][R][d] and tokens
+// [B][n][d] (either may be null).  One thread per 8 values of the rows that are read.  A tree has one root, its
+// last row (R = 1, root_row null); the graph of a packed batch has one per sequence, root_row[r] (-1: an empty
+// sequence, whose output is zero).
 __global__ void __launch_bounds__(256) readout_kernel(const bf16_t* __restrict__ h, bf16_t* __restrict__ root,
-                                                      bf16_t* __restrict__ tokens, int64_t chunks, int n, int N, int row_chunks) {
+                                                      bf16_t* __restrict__ tokens, int64_t chunks, int n, int N, int row_chunks,
+                                                      int R, const int32_t* __restrict__ root_row) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= chunks) return;
-    const int64_t row = i / row_chunks;   // over [B][n + 1]: the tokens, then the root
-    const int c = (int)(i - row * row_chunks), v = (int)(row % (n + 1));
-    const int64_t b = row / (n + 1);
+    const int64_t row = i / row_chunks;   // over [B][n + R]: the tokens, then the roots
+    const int c = (int)(i - row * row_chunks), v = (int)(row % (n + R));
+    const int64_t b = row / (n + R);
     bf16_t* dst = v < n ? tokens : root;
     if (!dst) return;
-    const uint4 x = *reinterpret_cast<const uint4*>(h + ((b * N + (v < n ? v : N - 1)) * row_chunks + c) * 8);
-    *reinterpret_cast<uint4*>(dst + ((v < n ? b * n + v : b) * row_chunks + c) * 8) = x;
+    const int src = v < n ? v : root_row ? root_row[v - n] : N - 1;
+    uint4 x = make_uint4(0u, 0u, 0u, 0u);
+    if (src >= 0) x = *reinterpret_cast<const uint4*>(h + ((b * N + src) * row_chunks + c) * 8);
+    *reinterpret_cast<uint4*>(dst + ((v < n ? b * n + v : b * R + (v - n)) * row_chunks + c) * 8) = x;
 }
 
 // the reverse: the gradient with respect to the last states is d_tokens on the token rows, d_root on the
 // root's row (a null one counts as zero) and zero on every other row
+// (first_root: the first root row -- N - 1 for a tree; root_seq: for the graph of a packed batch, the sequence of
+// every row from first_root on, else null)
 __global__ void __launch_bounds__(256) readout_bwd_kernel(const bf16_t* __restrict__ d_root, const bf16_t* __restrict__ d_tokens,
-                                                          bf16_t* __restrict__ dh, int64_t chunks, int n, int N, int row_chunks) {
+                                                          bf16_t* __restrict__ dh, int64_t chunks, int n, int N, int row_chunks,
+                                                          int R, int first_root, const int32_t* __restrict__ root_seq) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= chunks) return;
     const int64_t row = i / row_chunks;
@@ -397,7 +405,10 @@ __global__ void __launch_bounds__(256) readout_bwd_kernel(const bf16_t* __restri
     const int64_t b = row / N;
     uint4 x = make_uint4(0u, 0u, 0u, 0u);
     if (v < n && d_tokens) x = *reinterpret_cast<const uint4*>(d_tokens + ((b * n + v) * row_chunks + c) * 8);
-    if (v == N - 1 && d_root) x = *reinterpret_cast<const uint4*>(d_root + (b * row_chunks + c) * 8);
+    if (v >= first_root && d_root) {
+        const int r = root_seq ? root_seq[v - first_root] : 0;
+        x = *reinterpret_cast<const uint4*>(d_root + ((b * R + r) * row_chunks + c) * 8);
+    }
     *reinterpret_cast<uint4*>(dh + i * 8) = x;
 }
 
@@ -774,7 +785,7 @@ int bpt_layer_bwd(const bpt_graph_t* g, int32_t B, int32_t H, float scale, const
 
 size_t bpt_stack_fwd_workspace(const bpt_graph_t* g, int32_t B, int32_t H, int32_t d_ff, int32_t num_layers) {
     if (!g || B < 1 || H < 1 || d_ff < 8 || num_layers < 1 || num_layers > kMaxStackLayers) return 0;
-    if (g->batch > 0) return SIZE_MAX;   // embeddings and readout are laid out for the tree of one sequence
+    if (g->batch > 0 && B != 1) return SIZE_MAX;   // the graph of a packed batch is the whole batch
     if (bpt_layer_fwd_workspace(g, B, H, d_ff) == SIZE_MAX) return SIZE_MAX;
     return stack_buffers(g, B, H, d_ff, num_layers).total;
 }
@@ -784,7 +795,8 @@ int bpt_stack_fwd(const bpt_graph_t* g, int32_t B, int32_t H, int32_t num_layers
                   size_t workspace_bytes, void* stream) {
     if (!g || !rel || !E || !p || (!root && !tokens) || !workspace || B < 1 || H < 1 || num_layers < 1)
         return BPT_ERR_INVALID_ARG;
-    if (num_layers > kMaxStackLayers || g->batch > 0) return BPT_ERR_UNSUPPORTED;
+    if (num_layers > kMaxStackLayers) return BPT_ERR_UNSUPPORTED;
+    if (g->batch > 0 && (B != 1 || seq_len)) return BPT_ERR_INVALID_ARG;   // the graph of a packed batch is the whole batch
     for (int l = 0; l < num_layers; ++l) {
         if (!rel[l]) return BPT_ERR_INVALID_ARG;
         if (p[l].d_ff != p[0].d_ff) return BPT_ERR_UNSUPPORTED;   // one workspace size serves every layer
@@ -800,24 +812,27 @@ int bpt_stack_fwd(const bpt_graph_t* g, int32_t B, int32_t H, int32_t num_layers
     const int row_chunks = H * kD / 8;
     const int64_t chunks = rows * row_chunks;
     BPT_LAUNCH("initial_states_kernel", initial_states_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st,
-               static_cast<const bf16_t*>(E), reinterpret_cast<bf16_t*>(ws), chunks, g->n, g->num_nodes, row_chunks);
+               static_cast<const bf16_t*>(E), reinterpret_cast<bf16_t*>(ws), chunks, g->n_tokens, g->num_nodes, row_chunks);
     BPT_HIP(hipGetLastError());
     for (int l = 0; l < num_layers; ++l) {
         const int rc = bpt_layer_fwd(g, B, H, scale, seq_len, rel[l], ws + S.state_bytes * l, &p[l], ws + S.state_bytes * (l + 1),
                                      ws + S.layers_at + S.layer_bytes * l, S.layer_bytes, stream);
         if (rc) return rc;
     }
-    const int64_t out_chunks = (int64_t)B * (g->n + 1) * row_chunks;
+    // a tree has one root, its last row; the graph of a packed batch one per sequence
+    const int roots = g->batch > 0 ? g->batch : 1;
+    const int64_t out_chunks = (int64_t)B * (g->n_tokens + roots) * row_chunks;
     BPT_LAUNCH("readout_kernel", readout_kernel, dim3((unsigned)((out_chunks + 255) / 256)), dim3(256), 0, st,
                reinterpret_cast<const bf16_t*>(ws + S.state_bytes * num_layers), static_cast<bf16_t*>(root),
-               static_cast<bf16_t*>(tokens), out_chunks, g->n, g->num_nodes, row_chunks);
+               static_cast<bf16_t*>(tokens), out_chunks, g->n_tokens, g->num_nodes, row_chunks, roots,
+               static_cast<const int32_t*>(g->batch > 0 ? g->d_root_row : nullptr));
     BPT_HIP(hipGetLastError());
     return BPT_OK;
 }
 
 size_t bpt_stack_bwd_workspace(const bpt_graph_t* g, int32_t B, int32_t H, int32_t d_ff) {
     if (!g || B < 1 || H < 1 || d_ff < 8) return 0;
-    if (g->batch > 0) return SIZE_MAX;
+    if (g->batch > 0 && B != 1) return SIZE_MAX;
     const size_t layer = bpt_layer_bwd_workspace(g, B, H, d_ff);
     if (layer == SIZE_MAX) return SIZE_MAX;
     return layer ? 2 * align_up((size_t)B * g->num_nodes * H * kD * 2) + layer : 0;
@@ -830,7 +845,8 @@ int bpt_stack_bwd(const bpt_graph_t* g, int32_t B, int32_t H, int32_t num_layers
     if (!g || !rel || !p || !fwd_workspace || (!d_root && !d_tokens) || !dE || !d_rel || !grads || !workspace || B < 1 ||
         H < 1 || num_layers < 1)
         return BPT_ERR_INVALID_ARG;
-    if (num_layers > kMaxStackLayers || g->batch > 0) return BPT_ERR_UNSUPPORTED;
+    if (num_layers > kMaxStackLayers) return BPT_ERR_UNSUPPORTED;
+    if (g->batch > 0 && (B != 1 || seq_len)) return BPT_ERR_INVALID_ARG;
     for (int l = 0; l < num_layers; ++l) {
         if (!rel[l] || !d_rel[l]) return BPT_ERR_INVALID_ARG;
         if (p[l].d_ff != p[0].d_ff) return BPT_ERR_UNSUPPORTED;
@@ -853,7 +869,8 @@ int bpt_stack_bwd(const bpt_graph_t* g, int32_t B, int32_t H, int32_t num_layers
     const int64_t chunks = rows * row_chunks;
     BPT_LAUNCH("readout_bwd_kernel", readout_bwd_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st,
                static_cast<const bf16_t*>(d_root), static_cast<const bf16_t*>(d_tokens), reinterpret_cast<bf16_t*>(dh[0]), chunks,
-               g->n, g->num_nodes, row_chunks);
+               g->n_tokens, g->num_nodes, row_chunks, g->batch > 0 ? g->batch : 1, g->batch > 0 ? g->first_root : g->num_nodes - 1,
+               static_cast<const int32_t*>(g->batch > 0 ? g->d_root_seq : nullptr));
     BPT_HIP(hipGetLastError());
     int cur = 0;
     for (int l = num_layers - 1; l >= 0; --l, cur ^= 1) {
@@ -863,10 +880,10 @@ int bpt_stack_bwd(const bpt_graph_t* g, int32_t B, int32_t H, int32_t num_layers
         if (rc) return rc;
     }
     // the embeddings are the token rows of the first states; the zero rows of the spans have no parameter behind them
-    const int64_t out_chunks = (int64_t)B * (g->n + 1) * row_chunks;
+    const int64_t out_chunks = (int64_t)B * (g->n_tokens + 1) * row_chunks;
     BPT_LAUNCH("readout_kernel", readout_kernel, dim3((unsigned)((out_chunks + 255) / 256)), dim3(256), 0, st,
-               reinterpret_cast<const bf16_t*>(dh[cur]), static_cast<bf16_t*>(nullptr), static_cast<bf16_t*>(dE), out_chunks, g->n,
-               g->num_nodes, row_chunks);
+               reinterpret_cast<const bf16_t*>(dh[cur]), static_cast<bf16_t*>(nullptr), static_cast<bf16_t*>(dE), out_chunks,
+               g->n_tokens, g->num_nodes, row_chunks, 1, static_cast<const int32_t*>(nullptr));
     BPT_HIP(hipGetLastError());
     return BPT_OK;
 }

@@ -111,6 +111,59 @@ def test_stack_forward_and_backward(n, k, causal, B, heads, d_ff, lengths, decis
     g.destroy()
 
 
+@pytest.mark.parametrize("n,k,causal,heads,d_ff,lengths", [
+    (256, 3, False, 2, 256, [256, 150, 31, 0, 1]), (512, 4, True, 4, 512, [77, 512, 300]),
+])
+def test_stack_on_the_graph_of_a_packed_batch(n, k, causal, heads, d_ff, lengths):
+    # one graph for the batch (bpt_build_batch_graph): the embeddings and the token outputs are [1][T][d], the tokens of
+    # all sequences in row order, and there is one root per sequence (zero for an empty one); the oracle runs the
+    # padded trees with the lengths
+    print("stack on a packed batch", n, k, causal, heads, d_ff, lengths, flush=True)
+    B = len(lengths)
+    E, rels, params, d_root, d_tokens = make_stack(n, k, causal, B, heads, d_ff, 700 + n + heads, True)
+    tok = np.concatenate([np.stack([np.full(length, b), np.arange(length)]) for b, length in enumerate(lengths)], axis=1)
+    live = [b for b, length in enumerate(lengths) if length >= 1]
+    g = bpt.bpt_build_batch_graph(n, k, causal, lengths)
+    assert g.n_tokens == tok.shape[1]
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(torch.bfloat16).cuda()
+    Ed, Rd, Pd = dev(E[tok[0], tok[1]][None]), [dev(r) for r in rels], [to_dev(p) for p in params]
+    fws, bws = bpt.stack_workspace_bytes(g, 1, heads, d_ff, LAYERS)
+    ws_f = torch.empty(fws + 256, dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(bws + 256, dtype=torch.uint8, device="cuda")
+    root, tokens = bpt.bpt_stack_fwd(g, Ed, Rd, Pd, heads, scale=0.125, workspace=ws_f)
+    dE, d_rels, grads = bpt.bpt_stack_bwd(g, Ed, Rd, Pd, heads, ws_f, dev(d_root), dev(d_tokens[tok[0], tok[1]][None]),
+                                          scale=0.125, workspace=ws_b)
+    torch.cuda.synchronize()
+    assert tuple(root.shape) == (B, heads * 64) and tuple(tokens.shape) == tuple(Ed.shape)
+    # the oracle on the sequences that exist (an empty one has no graph), read at the tokens that exist
+    sub = lambda a: np.ascontiguousarray(a[live])
+    ll = [lengths[b] for b in live]
+    ref_root, ref_tokens, _ = stack_forward(n, k, causal, heads, sub(E), rels, params, 0.125, lengths=ll)
+    f64 = lambda t: t.float().cpu().numpy().astype(np.float64)
+    pos = {b: i for i, b in enumerate(live)}
+    tb = np.array([pos[b] for b in tok[0]])
+    err = max(float(np.abs(f64(root)[live] - ref_root).max()), float(np.abs(f64(tokens)[0] - ref_tokens[tb, tok[1]]).max()))
+    print("   forward max-abs error %.3g" % err, flush=True)
+    assert err <= TOL * LAYERS, err
+    for b in range(B):
+        if b not in live:
+            assert float(root[b].float().abs().max()) == 0.0
+    ref_dE, ref_grads = stack_backward(n, k, causal, heads, sub(E), rels, params, sub(d_root), sub(d_tokens), 0.125, lengths=ll)
+    rel_err = lambda a, r: float(np.abs(a - r).max()) / max(float(np.abs(r).max()), 1e-30)
+    worst = {"dE": rel_err(f64(dE)[0], ref_dE[tb, tok[1]])}
+    for layer in range(LAYERS):
+        worst["dRel%d" % layer] = rel_err(f64(d_rels[layer]), ref_grads[layer]["dRel"])
+        for name in GRADS:
+            worst[name + str(layer)] = rel_err(f64(grads[layer][name]), ref_grads[layer][name])
+    top = sorted(worst.items(), key=lambda kv: -kv[1])[:4]
+    print("   backward, largest relative max-abs errors", [(k_, float("%.2g" % v)) for k_, v in top], flush=True)
+    for name, v in worst.items():
+        assert np.isfinite(v) and v <= BWD_TOL_DECISIVE * LAYERS, (name, v)
+    with pytest.raises(Exception):                      # the graph of a packed batch is the whole batch
+        bpt.bpt_stack_fwd(g, torch.cat([Ed, Ed]), Rd, Pd, heads)
+    g.destroy()
+
+
 def test_stack_outputs_are_optional():
     n, k, B, heads, d_ff = 128, 2, 2, 1, 64
     E, rels, params, d_root, d_tokens = make_stack(n, k, False, B, heads, d_ff, 900, True)
