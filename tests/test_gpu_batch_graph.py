@@ -239,6 +239,23 @@ def test_nothing_is_written_outside_the_rows_of_a_batch_graph():
     g.destroy()
 
 
+def test_long_sequences_in_a_batch_graph():
+    run_attention_case("bf16", 16384, 4, True, 1, [16384, 9000, 33])
+
+
+def test_the_forward_that_allocates_nothing_takes_a_batch_graph():
+    g = bpt.bpt_build_batch_graph(2048, 4, False, [2048, 700, 1, 1300])
+    gen = torch.Generator(device="cuda").manual_seed(11)
+    Q, K, V = (torch.randn(1, 2, g.num_nodes, 64, device="cuda", generator=gen).to(torch.bfloat16) for _ in range(3))
+    R = (0.1 * torch.randn(g.num_levels, g.rel_width, 64, device="cuda", generator=gen)).to(torch.bfloat16)
+    out0, lse0 = bpt.bpt_attn_fwd(g, Q, K, V, R)
+    out1, lse1 = torch.full_like(Q, 7.0), torch.full(Q.shape[:3], 7.0, dtype=torch.float32, device="cuda")
+    bpt.bpt_attn_fwd_static(g, Q, K, V, R, out1, lse1)
+    torch.cuda.synchronize()
+    assert torch.equal(out0, out1) and torch.equal(lse0, lse1)
+    g.destroy()
+
+
 def test_a_batch_of_32_sentences():
     # the classification workload's batch: 32 sentences of very different lengths on trees over 512 tokens
     rng = np.random.default_rng(32)
