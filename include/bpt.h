@@ -133,6 +133,18 @@ int bpt_build_graph(int32_t n, int32_t k, int32_t causal, void* stream, bpt_grap
 int bpt_build_batch_graph(int32_t n, int32_t k, int32_t causal, const int32_t* lengths, int32_t batch,
                           void* stream, bpt_graph_t** out);
 
+/* The same for callers that build a graph for every batch they see (training on sentences): on an
+ * existing graph `tree` of bpt_build_graph(n, k, causal), which the new graph shares instead of
+ * building its own (the caller keeps `tree` alive until the new graph is destroyed; both on the
+ * current device), and, with with_edges == 0, without the batch's own CSR, transposed adjacency and
+ * gather schedules: only the row layout and the small tables the matrix-core kernels need are made
+ * (host arithmetic and four small copies).  Such a graph serves every call that runs on the
+ * matrix-core kernels (see above; also the layer and stack calls); the graph accessors and calls
+ * that would need the gather kernels return BPT_ERR_UNSUPPORTED (workspace queries SIZE_MAX), and
+ * bpt_graph_info reports 0 edges. */
+int bpt_build_batch_graph_on(const bpt_graph_t* tree, const int32_t* lengths, int32_t batch,
+                             int32_t with_edges, void* stream, bpt_graph_t** out);
+
 /* Row layout of a graph: *batch = sequences in it (1 for bpt_build_graph), *n_tokens = token
  * rows (they come first), and, into host arrays of num_levels * batch entries indexed
  * [level * batch + b], first_row = row of node (level, 0) of sequence b and row_count = nodes

@@ -21,7 +21,7 @@ BPT_OK, BPT_ERR_INVALID_ARG, BPT_ERR_UNSUPPORTED, BPT_ERR_ALLOC, BPT_ERR_LAUNCH,
 BPT_STATIC_SCRATCH_BYTES = 32 << 20
 
 EXPORTS = [
-    "bpt_build_graph", "bpt_build_batch_graph", "bpt_graph_layout", "bpt_graph_info", "bpt_graph_csr", "bpt_graph_transposed", "bpt_graph_to_host",
+    "bpt_build_graph", "bpt_build_batch_graph", "bpt_build_batch_graph_on", "bpt_graph_layout", "bpt_graph_info", "bpt_graph_csr", "bpt_graph_transposed", "bpt_graph_to_host",
     "bpt_graph_transposed_to_host", "bpt_graph_destroy", "bpt_attn_fwd_workspace", "bpt_attn_bwd_workspace",
     "bpt_attn_fwd", "bpt_attn_fwd_static", "bpt_attn_bwd", "bpt_attn_bwd_query_side", "bpt_attn_bwd_key_side", "bpt_profile_enable",
     "bpt_profile_report", "bpt_calibrate_gather", "bpt_layer_fwd_workspace", "bpt_layer_fwd", "bpt_layer_bwd_workspace", "bpt_layer_bwd",
@@ -74,6 +74,8 @@ def load_library() -> ctypes.CDLL:
     L.bpt_build_graph.argtypes = [i32, i32, i32, vp, P(vp)]
     L.bpt_build_batch_graph.restype = ctypes.c_int
     L.bpt_build_batch_graph.argtypes = [i32, i32, i32, vp, i32, vp, P(vp)]
+    L.bpt_build_batch_graph_on.restype = ctypes.c_int
+    L.bpt_build_batch_graph_on.argtypes = [vp, vp, i32, i32, vp, P(vp)]
     L.bpt_graph_layout.restype = ctypes.c_int
     L.bpt_graph_layout.argtypes = [vp, P(i32), P(i32), vp, vp]
     L.bpt_graph_info.restype = ctypes.c_int
@@ -150,11 +152,18 @@ def _stream_ptr() -> int:
 class Graph:
     """Device-resident binary-partition graph (bpt_build_graph; with `lengths`, bpt_build_batch_graph)."""
 
-    def __init__(self, n: int, k: int, causal: bool, lengths=None):
+    def __init__(self, n: int, k: int, causal: bool, lengths=None, tree: "Optional[Graph]" = None, with_edges: bool = True):
         L = load_library()
         handle = ctypes.c_void_p()
         self.is_batch = lengths is not None
-        if lengths is None:
+        self._tree = tree      # a shared tree has to outlive this graph
+        if tree is not None:
+            lens = np.ascontiguousarray(lengths, dtype=np.int32)
+            if lens.ndim != 1:
+                raise ValueError("lengths must be one-dimensional")
+            _check(L.bpt_build_batch_graph_on(tree.handle, lens.ctypes.data, int(lens.size), int(bool(with_edges)), _stream_ptr(),
+                                              ctypes.byref(handle)), "bpt_build_batch_graph_on(batch=%d)" % lens.size)
+        elif lengths is None:
             _check(L.bpt_build_graph(int(n), int(k), int(bool(causal)), _stream_ptr(), ctypes.byref(handle)),
                    "bpt_build_graph(n=%d, k=%d, causal=%d)" % (n, k, causal))
         else:
@@ -237,6 +246,12 @@ def bpt_build_graph(n: int, k: int, causal: bool) -> Graph:
 def bpt_build_batch_graph(n: int, k: int, causal: bool, lengths) -> Graph:
     """One graph for a batch of sequences of the given lengths, rows packed (see include/bpt.h)."""
     return Graph(n, k, causal, lengths)
+
+
+def bpt_build_batch_graph_on(tree: Graph, lengths, with_edges: bool = False) -> Graph:
+    """The same sharing an existing graph of (n, k, causal); without edge lists it is made by host arithmetic and a few
+    small copies and serves the calls that run on the matrix-core kernels."""
+    return Graph(tree.n, tree.k, tree.causal, lengths, tree=tree, with_edges=with_edges)
 
 
 def _shape_of(g: Graph, x: torch.Tensor, scale: Optional[float], seq_len: Optional[torch.Tensor] = None,

@@ -79,7 +79,7 @@ int check_shape(const bpt_graph* g, const bpt_shape_t* s) {
     // a batch graph carries the lengths itself; dropout masks are defined on the nodes of one tree
     if (g->batch > 0 && s->seq_len) return BPT_ERR_INVALID_ARG;
     if (g->batch > 0 && s->dropout_p > 0.f) return BPT_ERR_UNSUPPORTED;
-    if ((int64_t)s->B * s->H > (int64_t)INT32_MAX / std::max(g->fwd.num_tiles, g->tr.num_tiles))
+    if ((int64_t)s->B * s->H > (int64_t)INT32_MAX / std::max(1, std::max(g->fwd.num_tiles, g->tr.num_tiles)))
         return BPT_ERR_UNSUPPORTED;
     if ((int64_t)s->B * s->H * g->num_nodes > (int64_t)1 << 40) return BPT_ERR_UNSUPPORTED;
     if (g->num_edges >= ((int64_t)1 << 29)) return BPT_ERR_UNSUPPORTED;  // 32-bit byte offsets into the edge arrays
@@ -860,6 +860,7 @@ int backward(const bpt_graph_t* g, const bpt_shape_t* s, const void* Q, const vo
         g = g->tree;
         s = &view;
     } else {
+        if (!g->row_ptr) return BPT_ERR_UNSUPPORTED;   // a batch graph without its edge lists: matrix-core kernels only
         fill_common(a, g, s);
     }
     BwdPlan p;
@@ -904,6 +905,7 @@ size_t bpt_attn_fwd_workspace(const bpt_graph_t* g, const bpt_shape_t* s) {
     if (bpt::check_shape(g, s) != BPT_OK) return SIZE_MAX;
     bpt_shape_t view;
     if (bpt::packed_tiles(g, s, &view)) return bpt_attn_fwd_workspace(g->tree, &view);
+    if (!g->row_ptr) return SIZE_MAX;   // a batch graph without its edge lists runs the matrix-core kernels only
     return bpt::align_up((size_t)s->B * s->H *
                          std::max<size_t>(std::max(g->fwd.num_part, g->fwd_span.num_part), bpt::span_partials(g)) *
                          bpt::kPartStride * sizeof(float));
@@ -913,6 +915,7 @@ size_t bpt_attn_bwd_workspace(const bpt_graph_t* g, const bpt_shape_t* s) {
     if (bpt::check_shape(g, s) != BPT_OK) return SIZE_MAX;
     bpt_shape_t view;
     if (bpt::packed_tiles_bwd(g, s, &view)) return bpt_attn_bwd_workspace(g->tree, &view);
+    if (!g->row_ptr) return SIZE_MAX;
     bpt::BwdPlan p;
     if (bpt::plan_bwd(g, s, &p) != BPT_OK) return SIZE_MAX;
     return p.total;

@@ -829,7 +829,44 @@ int build(int32_t n, int32_t k, int32_t causal, hipStream_t st, bpt_graph* g) {
 
 // The graph of a batch of sequences (see the kernels above): same steps as build(), no dense tiles -- the
 // attention calls run the gather kernels on it.
-int build_batch(int32_t n, int32_t k, int32_t causal, const int32_t* lengths, int32_t B, hipStream_t st, bpt_graph* g) {
+// What the matrix-core kernels and the stack's readout need of a batch graph beyond its row layout: the tree of
+// one sequence with its tile metadata (built here, or shared), the lengths and the row deltas on the device, the
+// roots.  g->first_row / row_count / batch / n / num_levels are set.
+int batch_tables(int32_t n, int32_t k, int32_t causal, const int32_t* lengths, int32_t B, hipStream_t st, bpt_graph* g,
+                 const bpt_graph* shared_tree) {
+    const int num_levels = g->num_levels;
+    int rc;
+    if (shared_tree) {
+        g->tree = const_cast<bpt_graph*>(shared_tree);
+        g->owns_tree = false;
+    } else {
+        g->tree = new (std::nothrow) bpt_graph();
+        if (!g->tree) return BPT_ERR_ALLOC;
+        g->owns_tree = true;
+        if ((rc = build(n, k, causal, st, g->tree))) return rc;
+    }
+    g->ctx_levels = g->tree->ctx_levels;
+    std::vector<int32_t> h_delta((size_t)num_levels * B);
+    for (int l = 0; l < num_levels; ++l)
+        for (int b = 0; b < B; ++b) h_delta[(size_t)l * B + b] = g->first_row[(size_t)l * B + b] - (int32_t)level_offset(n, l);
+    std::vector<int32_t> h_len(lengths, lengths + B);
+    if ((rc = upload(h_delta, &g->d_delta)) || (rc = upload(h_len, &g->d_lengths))) return rc;
+    // the roots (the last level keeps one node of every sequence that has a token)
+    std::vector<int32_t> h_root_row((size_t)B), h_root_seq;
+    const size_t top = (size_t)(num_levels - 1) * B;
+    g->first_root = g->first_row[top];
+    for (int b = 0; b < B; ++b) {
+        h_root_row[b] = g->row_count[top + b] > 0 ? g->first_row[top + b] : -1;
+        if (g->row_count[top + b] > 0) h_root_seq.push_back(b);
+    }
+    if ((rc = upload(h_root_row, &g->d_root_row)) || (rc = upload(h_root_seq, &g->d_root_seq))) return rc;
+    return BPT_OK;
+}
+
+// shared_tree: an existing graph of (n, k, causal) to use for the matrix-core kernels instead of building one (not
+// owned); with_edges == false: the row layout only -- no CSR, no transposed adjacency, no gather schedules.
+int build_batch(int32_t n, int32_t k, int32_t causal, const int32_t* lengths, int32_t B, hipStream_t st, bpt_graph* g,
+                const bpt_graph* shared_tree = nullptr, bool with_edges = true) {
     const int num_levels = 32 - __builtin_clz((unsigned)n);
     g->n = n;
     g->k = k;
@@ -837,10 +874,15 @@ int build_batch(int32_t n, int32_t k, int32_t causal, const int32_t* lengths, in
     g->num_levels = num_levels;
     g->rel_width = 2 * (k + 1) + 1;
     g->batch = B;
-    BPT_HIP(hipGetDevice(&g->device));
-    hipDeviceProp_t prop;
-    BPT_HIP(hipGetDeviceProperties(&prop, g->device));
-    g->num_cus = prop.multiProcessorCount;
+    if (shared_tree) {
+        g->device = shared_tree->device;
+        g->num_cus = shared_tree->num_cus;
+    } else {
+        BPT_HIP(hipGetDevice(&g->device));
+        hipDeviceProp_t prop;
+        BPT_HIP(hipGetDeviceProperties(&prop, g->device));
+        g->num_cus = prop.multiProcessorCount;
+    }
 
     // row numbering (host): level-major over the batch
     g->first_row.assign((size_t)num_levels * B, 0);
@@ -862,6 +904,8 @@ int build_batch(int32_t n, int32_t k, int32_t causal, const int32_t* lengths, in
     if (T < 1) return BPT_ERR_INVALID_ARG;
     g->num_nodes = num_nodes;
     g->n_tokens = T;
+    int rc = batch_tables(n, k, causal, lengths, B, st, g, shared_tree);
+    if (rc || !with_edges) return rc;
 
     DeviceBuf tok_off, first_row, deg, counters, block_sums;
     BPT_HIP(tok_off.alloc(sizeof(int32_t) * h_tok_off.size()));
@@ -898,7 +942,7 @@ int build_batch(int32_t n, int32_t k, int32_t causal, const int32_t* lengths, in
     BPT_HIP(hipMalloc((void**)&g->row_ptr, sizeof(int32_t) * ((size_t)num_nodes + 1)));
     BPT_HIP(hipMalloc((void**)&g->col, sizeof(int32_t) * (size_t)e_all));
     BPT_HIP(hipMalloc((void**)&g->rel, sizeof(int32_t) * (size_t)e_all));
-    int rc = exclusive_scan(deg.as<int32_t>(), g->row_ptr, T, (int32_t)e_tok, block_sums.as<int32_t>(), st);
+    rc = exclusive_scan(deg.as<int32_t>(), g->row_ptr, T, (int32_t)e_tok, block_sums.as<int32_t>(), st);
     if (rc) return rc;
     hipLaunchKernelGGL(batch_fill_tokens, dim3(token_blocks), dim3(tb), 0, st, T, k, g->causal, B, tok_off.as<int32_t>(),
                        first_row.as<int32_t>(), g->row_ptr, g->col, g->rel);
@@ -942,27 +986,7 @@ int build_batch(int32_t n, int32_t k, int32_t causal, const int32_t* lengths, in
     BPT_HIP(hipMemcpyAsync(h_tptr.data(), g->t_ptr, sizeof(int32_t) * h_tptr.size(), hipMemcpyDeviceToHost, st));
     BPT_HIP(hipStreamSynchronize(st));
     if ((rc = make_schedule(h_ptr, 0, T, g->fwd))) return rc;
-    if ((rc = make_schedule(h_tptr, 0, num_nodes, g->tr))) return rc;
-
-    // 6. for the matrix-core kernels: the tree of one sequence with its tile metadata, the lengths and the row deltas
-    g->tree = new (std::nothrow) bpt_graph();
-    if (!g->tree) return BPT_ERR_ALLOC;
-    if ((rc = build(n, k, causal, st, g->tree))) return rc;
-    std::vector<int32_t> h_delta((size_t)num_levels * B);
-    for (int l = 0; l < num_levels; ++l)
-        for (int b = 0; b < B; ++b) h_delta[(size_t)l * B + b] = g->first_row[(size_t)l * B + b] - (int32_t)level_offset(n, l);
-    std::vector<int32_t> h_len(lengths, lengths + B);
-    if ((rc = upload(h_delta, &g->d_delta)) || (rc = upload(h_len, &g->d_lengths))) return rc;
-    // the roots (the last level keeps one node of every sequence that has a token)
-    std::vector<int32_t> h_root_row((size_t)B), h_root_seq;
-    const size_t top = (size_t)(num_levels - 1) * B;
-    g->first_root = g->first_row[top];
-    for (int b = 0; b < B; ++b) {
-        h_root_row[b] = g->row_count[top + b] > 0 ? g->first_row[top + b] : -1;
-        if (g->row_count[top + b] > 0) h_root_seq.push_back(b);
-    }
-    if ((rc = upload(h_root_row, &g->d_root_row)) || (rc = upload(h_root_seq, &g->d_root_seq))) return rc;
-    return BPT_OK;
+    return make_schedule(h_tptr, 0, num_nodes, g->tr);
 }
 
 }  // namespace
@@ -1115,7 +1139,7 @@ void bpt_graph_destroy(bpt_graph_t* g) {
     (void)hipFree(g->d_delta);
     (void)hipFree(g->d_root_row);
     (void)hipFree(g->d_root_seq);
-    bpt_graph_destroy(g->tree);
+    if (g->owns_tree) bpt_graph_destroy(g->tree);
     delete g;
 }
 
@@ -1169,6 +1193,33 @@ int bpt_build_batch_graph(int32_t n, int32_t k, int32_t causal, const int32_t* l
     return BPT_OK;
 }
 
+int bpt_build_batch_graph_on(const bpt_graph_t* tree, const int32_t* lengths, int32_t batch, int32_t with_edges, void* stream,
+                             bpt_graph_t** out) {
+    if (!out) return BPT_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!tree || tree->batch > 0 || !lengths || batch < 1) return BPT_ERR_INVALID_ARG;
+    if (batch > (1 << 16)) return BPT_ERR_UNSUPPORTED;
+    for (int32_t b = 0; b < batch; ++b)
+        if (lengths[b] < 0 || lengths[b] > tree->n) return BPT_ERR_INVALID_ARG;
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess || device != tree->device) return BPT_ERR_INVALID_ARG;
+    bpt_graph* g = new (std::nothrow) bpt_graph();
+    if (!g) return BPT_ERR_ALLOC;
+    int rc;
+    try {
+        rc = bpt::build_batch(tree->n, tree->k, tree->causal, lengths, batch, static_cast<hipStream_t>(stream), g, tree,
+                              with_edges != 0);
+    } catch (const std::bad_alloc&) {
+        rc = BPT_ERR_ALLOC;
+    }
+    if (rc != BPT_OK) {
+        bpt_graph_destroy(g);
+        return rc;
+    }
+    *out = g;
+    return BPT_OK;
+}
+
 int bpt_graph_layout(const bpt_graph_t* g, int32_t* batch, int32_t* n_tokens, int32_t* first_row, int32_t* row_count) {
     if (!g) return BPT_ERR_INVALID_ARG;
     if (batch) *batch = g->batch > 0 ? g->batch : 1;
@@ -1201,6 +1252,7 @@ int bpt_graph_info(const bpt_graph_t* g, int32_t* n, int32_t* k, int32_t* causal
 
 int bpt_graph_csr(const bpt_graph_t* g, const int32_t** row_ptr, const int32_t** col, const int32_t** rel) {
     if (!g) return BPT_ERR_INVALID_ARG;
+    if (!g->row_ptr) return BPT_ERR_UNSUPPORTED;   // a batch graph built without its edge lists
     if (row_ptr) *row_ptr = g->row_ptr;
     if (col) *col = g->col;
     if (rel) *rel = g->rel;
@@ -1209,6 +1261,7 @@ int bpt_graph_csr(const bpt_graph_t* g, const int32_t** row_ptr, const int32_t**
 
 int bpt_graph_transposed(const bpt_graph_t* g, const int32_t** t_ptr, const int32_t** t_src, const int32_t** t_eid) {
     if (!g) return BPT_ERR_INVALID_ARG;
+    if (!g->row_ptr) return BPT_ERR_UNSUPPORTED;   // a batch graph built without its edge lists
     if (t_ptr) *t_ptr = g->t_ptr;
     if (t_src) *t_src = g->t_src;
     if (t_eid) *t_eid = g->t_eid;
@@ -1222,6 +1275,7 @@ static int copy_out(int32_t* dst, const int32_t* src, size_t count) {
 
 int bpt_graph_to_host(const bpt_graph_t* g, int32_t* row_ptr, int32_t* col, int32_t* rel) {
     if (!g) return BPT_ERR_INVALID_ARG;
+    if (!g->row_ptr) return BPT_ERR_UNSUPPORTED;   // a batch graph built without its edge lists
     int rc;
     if ((rc = copy_out(row_ptr, g->row_ptr, (size_t)g->num_nodes + 1))) return rc;
     if ((rc = copy_out(col, g->col, (size_t)g->num_edges))) return rc;
@@ -1230,6 +1284,7 @@ int bpt_graph_to_host(const bpt_graph_t* g, int32_t* row_ptr, int32_t* col, int3
 
 int bpt_graph_transposed_to_host(const bpt_graph_t* g, int32_t* t_ptr, int32_t* t_src, int32_t* t_eid) {
     if (!g) return BPT_ERR_INVALID_ARG;
+    if (!g->row_ptr) return BPT_ERR_UNSUPPORTED;   // a batch graph built without its edge lists
     int rc;
     if ((rc = copy_out(t_ptr, g->t_ptr, (size_t)g->num_nodes + 1))) return rc;
     if ((rc = copy_out(t_src, g->t_src, (size_t)g->num_edges))) return rc;

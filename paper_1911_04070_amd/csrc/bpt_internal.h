@@ -89,6 +89,7 @@ struct bpt_graph {
     // batch graph, for the matrix-core kernels: the graph of one sequence of n tokens (their tile metadata), and on the
     // device the lengths [sequence] and delta[level][sequence] = first_row - first id of the level in that tree
     bpt_graph* tree = nullptr;
+    bool owns_tree = false;       // built by this graph (else shared with the caller, who keeps it alive)
     int32_t *d_lengths = nullptr, *d_delta = nullptr;
     // batch graph, for the stack's readout: the row of every sequence's root (-1: the sequence is empty), and for
     // the rows from first_root on (the root level) the sequence they belong to

@@ -65,6 +65,9 @@ def test_build_batch_graph_rejects_bad_arguments_on_the_host():
         assert lib.bpt_build_batch_graph(n, k, causal, lengths, batch, None, ctypes.byref(h)) == code, args
         assert h.value is None
     assert lib.bpt_build_batch_graph(64, 2, 0, lens, 1, None, None) == bpt.BPT_ERR_INVALID_ARG
+    h = ctypes.c_void_p(123)
+    assert lib.bpt_build_batch_graph_on(None, lens, 1, 0, None, ctypes.byref(h)) == bpt.BPT_ERR_INVALID_ARG and h.value is None
+    assert lib.bpt_build_batch_graph_on(None, lens, 1, 0, None, None) == bpt.BPT_ERR_INVALID_ARG
 
 
 def test_null_graph_is_an_error_everywhere():

@@ -256,6 +256,49 @@ def test_the_forward_that_allocates_nothing_takes_a_batch_graph():
     g.destroy()
 
 
+def test_batch_graphs_on_a_shared_tree():
+    # bpt_build_batch_graph_on: the tree of (n, k, causal) is built once and shared by the graphs of many batches; without
+    # edge lists such a graph is a few small tables, serves the matrix-core kernels and refuses the rest
+    n, k, causal, H = 1024, 4, False, 2
+    tree = bpt.bpt_build_graph(n, k, causal)
+    gen = torch.Generator(device="cuda").manual_seed(3)
+    for lengths in ([1024, 300, 33, 1, 0], [7, 900], [512] * 5):
+        full = bpt.bpt_build_batch_graph(n, k, causal, lengths)
+        with_e = bpt.bpt_build_batch_graph_on(tree, lengths, with_edges=True)
+        light = bpt.bpt_build_batch_graph_on(tree, lengths)
+        for g in (with_e, light):
+            assert (g.num_nodes, g.n_tokens, g.batch) == (full.num_nodes, full.n_tokens, full.batch)
+            assert np.array_equal(g.first_row, full.first_row) and np.array_equal(g.row_count, full.row_count)
+        for a, b in zip(full.csr_to_host() + full.transposed_to_host(), with_e.csr_to_host() + with_e.transposed_to_host()):
+            assert np.array_equal(a, b)
+        assert light.num_edges == 0
+        with pytest.raises(bpt.BptError):
+            light.csr_to_host()
+        Q, K, V, dO = (torch.randn(1, H, full.num_nodes, 64, device="cuda", generator=gen).to(torch.bfloat16) for _ in range(4))
+        R = (0.1 * torch.randn(full.num_levels, full.rel_width, 64, device="cuda", generator=gen)).to(torch.bfloat16)
+        out0, lse0 = bpt.bpt_attn_fwd(full, Q, K, V, R)
+        g0 = bpt.bpt_attn_bwd(full, Q, K, V, R, lse0, dO)
+        for g in (with_e, light):
+            out1, lse1 = bpt.bpt_attn_fwd(g, Q, K, V, R)
+            g1 = bpt.bpt_attn_bwd(g, Q, K, V, R, lse1, dO)
+            torch.cuda.synchronize()
+            assert torch.equal(out0, out1) and torch.equal(lse0, lse1)
+            for x, y in zip(g0, g1):
+                assert torch.equal(x, y)
+        # fp32 tensors run the gather kernels, which need the edge lists
+        Qf = Q.float()
+        bpt.bpt_attn_fwd(with_e, Qf, Qf, Qf, R.float())
+        with pytest.raises(bpt.BptError) as e:
+            bpt.bpt_attn_fwd(light, Qf, Qf, Qf, R.float())
+        assert e.value.status == bpt.BPT_ERR_UNSUPPORTED
+        for g in (full, with_e, light):
+            g.destroy()
+    with pytest.raises(bpt.BptError):       # a batch graph is no tree
+        b = bpt.bpt_build_batch_graph(n, k, causal, [5, 6])
+        bpt.bpt_build_batch_graph_on(b, [3])
+    tree.destroy()
+
+
 def test_a_batch_of_32_sentences():
     # the classification workload's batch: 32 sentences of very different lengths on trees over 512 tokens
     rng = np.random.default_rng(32)
