@@ -51,6 +51,27 @@ def test_batch_graph_is_bit_exact(n, k, causal, lengths):
     g.destroy()
 
 
+def test_random_batch_graphs_are_bit_exact():
+    rng = np.random.default_rng(2024)
+    for case in range(40):
+        n = int(2 ** rng.integers(1, 12))
+        k = int(rng.integers(1, 24))
+        causal = bool(rng.integers(0, 2))
+        B = int(rng.integers(1, 40))
+        lengths = [int(v) for v in rng.integers(0, n + 1, size=B)]
+        if sum(lengths) == 0:
+            lengths[-1] = 1
+        say("random batch graph", case, n, k, causal, lengths[:8], "..." if B > 8 else "")
+        want = oracle.build_batch_graph(n, k, causal, lengths)
+        g = bpt.bpt_build_batch_graph(n, k, causal, lengths)
+        row_ptr, col, rel = g.csr_to_host()
+        assert np.array_equal(row_ptr, want.row_ptr) and np.array_equal(col, want.col) and np.array_equal(rel, want.rel)
+        t_ptr, t_src, t_eid = g.transposed_to_host()
+        w_ptr, w_src, w_eid = oracle.transpose(want)
+        assert np.array_equal(t_ptr, w_ptr) and np.array_equal(t_src, w_src) and np.array_equal(t_eid, w_eid)
+        g.destroy()
+
+
 def test_batch_graph_of_full_sequences_is_the_single_graph_repeated():
     n, k = 256, 3
     one = bpt.bpt_build_graph(n, k, False)
