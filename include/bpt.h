@@ -292,11 +292,16 @@ typedef struct {
  * variance).  X and Y are [B][N][d] bf16, contiguous, N = 2n-1 rows per batch entry in node-id
  * order (span rows of the first layer are zero, Sec. 3.3); all nodes are updated from the same
  * X.  rel, scale and seq_len as for bpt_attn_fwd (with seq_len, rows of nodes that are not
- * kept hold unspecified values).  The dense maps run as rocBLAS GEMMs with fp32 accumulation;
+ * kept hold unspecified values).  The dense maps run as library GEMMs with fp32 accumulation
+ * (hipBLASLt, with b1 and the ReLU applied to the fp32 sums in the product's epilogue; rocBLAS for
+ * the weight gradients and for any product hipBLASLt has no algorithm for);
  * Q, K, V, the attention output, Z and the hidden FFN activations are stored in bf16 and stay
  * in the workspace for bpt_layer_bwd.
  * workspace: device memory of at least bpt_layer_fwd_workspace bytes; nothing is allocated
- * except, once per host thread and device, the rocBLAS handle.  H * 64 <= 2048.  Every tensor
+ * except, once per host thread and device, the two libraries' handles and 32 MiB of scratch
+ * memory for hipBLASLt, and the first call with a new shape times that library's candidate
+ * kernels on the caller's buffers (it synchronises with the stream, which therefore must not be
+ * capturing; later calls can be captured).  H * 64 <= 2048.  Every tensor
  * of the layer and stack calls (parameters and gradients included) starts on a 16-byte
  * boundary, else BPT_ERR_INVALID_ARG.  The layer and stack workspace queries return SIZE_MAX when
  * the attention calls would refuse the graph and shape, and the calls then BPT_ERR_UNSUPPORTED. */
@@ -323,8 +328,8 @@ typedef struct {
  * holds the activations the backward reads (Q, K, V, the attention output and lse, the two
  * pre-normalisation sums with their means and reciprocal deviations, Z, the hidden FFN
  * activations).  With seq_len, rows of dY of nodes that are not kept are taken as zero and
- * the same rows of dX are zero.  The dense maps run as rocBLAS GEMMs (bf16 operands: the
- * fp32 gradients of the attention are rounded to bf16 before their projections; fp32
+ * the same rows of dX are zero.  The dense maps run as library GEMMs as in the forward (bf16
+ * operands: the attention's backward writes its gradients rounded to bf16; fp32
  * accumulation); sums over rows (biases, gains) are formed in a fixed order, so results are
  * run-to-run identical as far as the GEMM library's are.  workspace: at least
  * bpt_layer_bwd_workspace bytes of device memory; nothing is allocated.  d_ff <= 8192. */

@@ -22,7 +22,7 @@ def build_library(verbose: bool = False) -> str:
     tmp = LIB + ".tmp.%d" % os.getpid()
     cmd = [hipcc] + FLAGS + ["-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", tmp]
     cmd += [os.path.join(CSRC, s) for s in SOURCES]
-    cmd += ["-L/opt/rocm/lib", "-lrocblas", "-Wl,-rpath,/opt/rocm/lib"]   # plain library GEMMs of the graph layer
+    cmd += ["-L/opt/rocm/lib", "-lrocblas", "-lhipblaslt", "-Wl,-rpath,/opt/rocm/lib"]   # plain library GEMMs of the graph layer
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)

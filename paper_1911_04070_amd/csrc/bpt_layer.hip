@@ -2,15 +2,19 @@
 //   Z = norm(X + [head_1 .. head_H] Wo),   Y = norm(Z + max(0, Z W1 + b1) W2 + b2)
 // for all 2n-1 nodes, forward and backward, and the loop over layers from the initial states
 // (embeddings on the token rows, zero on the span rows) to the root or token rows of the last
-// layer.  The dense maps are plain library GEMMs (rocBLAS,
+// layer.  The dense maps are plain library GEMMs (hipBLASLt, rocBLAS for the weight gradients;
 // bf16 operands, fp32 accumulation); attention is this library's own forward and backward on the
 // [B][N][H][64] layout the projections produce (no transposes); residual + bias + layer
 // normalisation, bias + ReLU, their backward counterparts and the fixed-order column sums are
 // the small kernels below.
 #include <hip/hip_runtime.h>
+#include <hipblaslt/hipblaslt.h>
 #include <rocblas/rocblas.h>
 
 #include <algorithm>
+#include <cstdlib>
+#include <string>
+#include <vector>
 
 #include "bpt_internal.h"
 
@@ -437,8 +441,159 @@ int gemm_rm(rocblas_handle h, int64_t M, int64_t N, int64_t K, const void* A, bo
         rocblas_datatype_f32_r, rocblas_gemm_algo_standard, 0, 0);
     return st == rocblas_status_success ? BPT_OK : BPT_ERR_LAUNCH;
 }
-int gemm_rm(rocblas_handle h, int64_t M, int N, int K, const void* A, const void* B, void* C, bool c_fp32) {
-    return gemm_rm(h, M, N, K, A, false, B, false, C, c_fp32);
+
+// The same product through hipBLASLt, whose epilogue can add a bias row and apply the ReLU while the sums are
+// still fp32 in registers (Sec. 3.1 eq. (3): max(0, Z W1 + b1) without a pass of its own), and whose kernel
+// choice for the tall products of the layer (65 532 x 512..2048) is 5-15 % faster than the one behind
+// rocblas_gemm_ex.  A plan (descriptor, layouts, algorithm) per distinct product, made on first use and kept,
+// per host thread and device like the rocBLAS handle; the first use of a product must therefore lie outside a
+// stream capture.  A product hipBLASLt has no algorithm for reports false and the caller takes the rocBLAS path.
+struct LtPlan {
+    int64_t M, N, K, lda, ldc;
+    bool ta, tb, c_fp32, bias_relu;
+    hipblasLtMatmulDesc_t desc;
+    hipblasLtMatrixLayout_t la, lb, lc;
+    hipblasLtMatmulAlgo_t algo;
+    size_t ws_bytes;
+};
+struct LtContext {
+    hipblasLtHandle_t handle = nullptr;
+    void* ws = nullptr;               // the algorithms' scratch memory, kept until the process ends
+    std::vector<LtPlan> plans;
+    bool failed = false;
+};
+constexpr size_t kLtWorkspace = (size_t)32 << 20;
+constexpr int kLtCandidates = 12, kLtTimedRuns = 3;
+LtContext* lt_context(int device) {
+    thread_local LtContext ctx[64];
+    if (device < 0 || device >= 64) return nullptr;
+    LtContext& c = ctx[device];
+    if (c.failed) return nullptr;
+    if (!c.handle) {
+        if (hipblasLtCreate(&c.handle) != HIPBLAS_STATUS_SUCCESS || hipMalloc(&c.ws, kLtWorkspace) != hipSuccess) {
+            c.failed = true;
+            (void)hipGetLastError();
+            return nullptr;
+        }
+    }
+    return &c;
+}
+// C[M][N] = op(A) op(B) (+ bias[N], then max(0, .) with bias_relu), arguments as gemm_rm's with beta = 0
+bool gemm_lt(int device, hipStream_t st, int64_t M, int64_t N, int64_t K, const void* A, bool ta, const void* B, bool tb, void* C,
+             bool c_fp32, int64_t lda, int64_t ldc, const float* bias_relu) {
+    LtContext* c = lt_context(device);
+    if (!c) return false;
+    const int64_t lda_ = lda ? lda : (ta ? M : K), ldc_ = ldc ? ldc : N;
+    LtPlan* plan = nullptr;
+    for (LtPlan& q : c->plans)
+        if (q.M == M && q.N == N && q.K == K && q.lda == lda_ && q.ldc == ldc_ && q.ta == ta && q.tb == tb && q.c_fp32 == c_fp32 &&
+            q.bias_relu == (bias_relu != nullptr)) {
+            plan = &q;
+            break;
+        }
+    if (!plan) {
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(st, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) return false;
+        LtPlan q = {M, N, K, lda_, ldc_, ta, tb, c_fp32, bias_relu != nullptr, nullptr, nullptr, nullptr, nullptr, {}, 0};
+        // column-major view: C^T [N x M] = op(B)^T [N x K] op(A)^T [K x M] on the same buffers
+        const hipblasOperation_t op_first = tb ? HIPBLAS_OP_T : HIPBLAS_OP_N, op_second = ta ? HIPBLAS_OP_T : HIPBLAS_OP_N;
+        const hipDataType ctype = c_fp32 ? HIP_R_32F : HIP_R_16BF;
+        bool ok = hipblasLtMatmulDescCreate(&q.desc, HIPBLAS_COMPUTE_32F, HIP_R_32F) == HIPBLAS_STATUS_SUCCESS;
+        ok = ok && hipblasLtMatmulDescSetAttribute(q.desc, HIPBLASLT_MATMUL_DESC_TRANSA, &op_first, sizeof(op_first)) == HIPBLAS_STATUS_SUCCESS;
+        ok = ok && hipblasLtMatmulDescSetAttribute(q.desc, HIPBLASLT_MATMUL_DESC_TRANSB, &op_second, sizeof(op_second)) == HIPBLAS_STATUS_SUCCESS;
+        if (ok && bias_relu) {
+            const hipblasLtEpilogue_t epi = HIPBLASLT_EPILOGUE_RELU_BIAS;
+            const hipDataType btype = HIP_R_32F;
+            ok = hipblasLtMatmulDescSetAttribute(q.desc, HIPBLASLT_MATMUL_DESC_EPILOGUE, &epi, sizeof(epi)) == HIPBLAS_STATUS_SUCCESS &&
+                 hipblasLtMatmulDescSetAttribute(q.desc, HIPBLASLT_MATMUL_DESC_BIAS_DATA_TYPE, &btype, sizeof(btype)) == HIPBLAS_STATUS_SUCCESS &&
+                 hipblasLtMatmulDescSetAttribute(q.desc, HIPBLASLT_MATMUL_DESC_BIAS_POINTER, &bias_relu, sizeof(bias_relu)) == HIPBLAS_STATUS_SUCCESS;
+        }
+        ok = ok && hipblasLtMatrixLayoutCreate(&q.la, HIP_R_16BF, tb ? K : N, tb ? N : K, tb ? K : N) == HIPBLAS_STATUS_SUCCESS;
+        ok = ok && hipblasLtMatrixLayoutCreate(&q.lb, HIP_R_16BF, ta ? M : K, ta ? K : M, lda_) == HIPBLAS_STATUS_SUCCESS;
+        ok = ok && hipblasLtMatrixLayoutCreate(&q.lc, ctype, N, M, ldc_) == HIPBLAS_STATUS_SUCCESS;
+        hipblasLtMatmulPreference_t pref = nullptr;
+        ok = ok && hipblasLtMatmulPreferenceCreate(&pref) == HIPBLAS_STATUS_SUCCESS;
+        ok = ok && hipblasLtMatmulPreferenceSetAttribute(pref, HIPBLASLT_MATMUL_PREF_MAX_WORKSPACE_BYTES, &kLtWorkspace, sizeof(kLtWorkspace)) == HIPBLAS_STATUS_SUCCESS;
+        hipblasLtMatmulHeuristicResult_t res[kLtCandidates];
+        int found = 0;
+        ok = ok && hipblasLtMatmulAlgoGetHeuristic(c->handle, q.desc, q.la, q.lb, q.lc, q.lc, pref, kLtCandidates, res, &found) ==
+                       HIPBLAS_STATUS_SUCCESS;
+        if (pref) hipblasLtMatmulPreferenceDestroy(pref);
+        // the library's candidates, timed on the caller's own buffers (beta = 0: what they write is overwritten by
+        // the product proper); the fastest is kept for this process
+        int best = -1;
+        float best_ms = 0.f;
+        hipEvent_t e0 = nullptr, e1 = nullptr;
+        if (ok && found > 1 && (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)) found = 1;
+        const float one = 1.f, zero = 0.f;
+        for (int i = 0; ok && i < found; ++i) {
+            if (res[i].state != HIPBLAS_STATUS_SUCCESS || res[i].workspaceSize > kLtWorkspace) continue;
+            if (found == 1) {
+                best = i;
+                break;
+            }
+            bool ran = true;
+            for (int rep = 0; rep < kLtTimedRuns + 1 && ran; ++rep) {   // the first run is not timed
+                if (rep == 1) ran = hipEventRecord(e0, st) == hipSuccess;
+                ran = ran && hipblasLtMatmul(c->handle, q.desc, &one, B, q.la, A, q.lb, &zero, C, q.lc, C, q.lc, &res[i].algo, c->ws,
+                                             kLtWorkspace, st) == HIPBLAS_STATUS_SUCCESS;
+            }
+            float ms = 0.f;
+            ran = ran && hipEventRecord(e1, st) == hipSuccess && hipEventSynchronize(e1) == hipSuccess &&
+                  hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
+            if (ran && (best < 0 || ms < best_ms)) {
+                best = i;
+                best_ms = ms;
+            }
+        }
+        if (e0) (void)hipEventDestroy(e0);
+        if (e1) (void)hipEventDestroy(e1);
+        ok = ok && best >= 0;
+        if (ok) {
+            q.algo = res[best].algo;
+            q.ws_bytes = res[best].workspaceSize;
+        } else {   // remembered as a product to leave to rocBLAS
+            if (q.lc) hipblasLtMatrixLayoutDestroy(q.lc);
+            if (q.lb) hipblasLtMatrixLayoutDestroy(q.lb);
+            if (q.la) hipblasLtMatrixLayoutDestroy(q.la);
+            if (q.desc) hipblasLtMatmulDescDestroy(q.desc);
+            q.desc = nullptr;
+        }
+        c->plans.push_back(q);
+        plan = &c->plans.back();
+    }
+    if (!plan->desc) return false;
+    if (bias_relu && hipblasLtMatmulDescSetAttribute(plan->desc, HIPBLASLT_MATMUL_DESC_BIAS_POINTER, &bias_relu, sizeof(bias_relu)) !=
+                         HIPBLAS_STATUS_SUCCESS)
+        return false;
+    const float one = 1.f, zero = 0.f;
+    return hipblasLtMatmul(c->handle, plan->desc, &one, B, plan->la, A, plan->lb, &zero, C, plan->lc, C, plan->lc, &plan->algo, c->ws,
+                           kLtWorkspace, st) == HIPBLAS_STATUS_SUCCESS;
+}
+
+// the dense products of the layer: hipBLASLt where it has an algorithm (always, with the bias + ReLU epilogue or
+// without), else rocBLAS (and the caller's own bias + ReLU kernel: *fused says which).  BPT_LAYER_BLAS=rocblas in
+// the environment keeps everything on rocBLAS (for comparisons).
+struct Blas {
+    rocblas_handle h;
+    int device;
+    hipStream_t st;
+};
+bool lt_enabled() {
+    static const bool on = [] {
+        const char* e = getenv("BPT_LAYER_BLAS");
+        return !(e && std::string(e) == "rocblas");
+    }();
+    return on;
+}
+int gemm(const Blas& b, int64_t M, int64_t N, int64_t K, const void* A, bool ta, const void* B, bool tb, void* C, bool c_fp32,
+         int64_t lda = 0, int64_t ldc = 0, const float* bias_relu = nullptr, bool* fused = nullptr) {
+    if (fused) *fused = false;
+    if (lt_enabled() && gemm_lt(b.device, b.st, M, N, K, A, ta, B, tb, C, c_fp32, lda, ldc, bias_relu)) {
+        if (fused) *fused = true;
+        return BPT_OK;
+    }
+    return gemm_rm(b.h, M, N, K, A, ta, B, tb, C, c_fp32, 0.f, lda, ldc);
 }
 
 size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -643,6 +798,7 @@ int bpt_layer_fwd(const bpt_graph_t* g, int32_t B, int32_t H, float scale, const
     hipStream_t st = static_cast<hipStream_t>(stream);
     rocblas_handle h = blas_handle(g->device);
     if (!h || rocblas_set_stream(h, st) != rocblas_status_success) return BPT_ERR_LAUNCH;
+    const Blas bl = {h, g->device, st};
     unsigned char* ws = static_cast<unsigned char*>(workspace);
     bf16_t* qkvo = reinterpret_cast<bf16_t*>(ws + L.qkvo);
     bf16_t* wqkv = reinterpret_cast<bf16_t*>(ws + L.wqkv);
@@ -662,22 +818,25 @@ int bpt_layer_fwd(const bpt_graph_t* g, int32_t B, int32_t H, float scale, const
     BPT_LAUNCH("pack_qkv_weights_kernel", pack_qkv_weights_kernel, dim3((unsigned)((wchunks + 255) / 256), 3), dim3(256), 0, st, pa,
                wchunks, d);
     BPT_HIP(hipGetLastError());
-    if ((rc = gemm_rm(h, rows, 3 * d, d, X, false, wqkv, false, qkvo, false, 0.f, 0, 4 * d))) return rc;
+    if ((rc = gemm(bl, rows, 3 * d, d, X, false, wqkv, false, qkvo, false, 0, 4 * d))) return rc;
     if ((rc = bpt_attn_fwd(g, &s, q, k, v, rel, o, lse, ws + L.attn, attn_ws, stream))) return rc;
     // Z = norm(X + O Wo)
-    if ((rc = gemm_rm(h, rows, d, d, o, false, p->Wo, false, acc1, true, 0.f, 4 * d))) return rc;
+    if ((rc = gemm(bl, rows, d, d, o, false, p->Wo, false, acc1, true, 4 * d))) return rc;
     const unsigned ln_blocks = (unsigned)((rows + 3) / 4);
     BPT_LAUNCH("residual_layer_norm_kernel", residual_layer_norm_kernel, dim3(ln_blocks), dim3(256), 0, st,
                static_cast<const bf16_t*>(X), acc1, static_cast<const float*>(nullptr), p->g1, p->beta1, static_cast<bf16_t*>(z),
                st1, rows, d, eps);
     BPT_HIP(hipGetLastError());
     // Y = norm(Z + max(0, Z W1 + b1) W2 + b2)
-    if ((rc = gemm_rm(h, rows, d_ff, d, z, p->W1, f1, false))) return rc;
-    const int64_t chunks = rows * d_ff / 8;
-    BPT_LAUNCH("bias_relu_kernel", bias_relu_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st,
-               static_cast<bf16_t*>(f1), p->b1, chunks, d_ff);
-    BPT_HIP(hipGetLastError());
-    if ((rc = gemm_rm(h, rows, d, d_ff, f1, p->W2, acc2, true))) return rc;
+    bool fused = false;   // bias + ReLU in the product's epilogue, on the fp32 sums
+    if ((rc = gemm(bl, rows, d_ff, d, z, false, p->W1, false, f1, false, 0, 0, p->b1, &fused))) return rc;
+    if (!fused) {
+        const int64_t chunks = rows * d_ff / 8;
+        BPT_LAUNCH("bias_relu_kernel", bias_relu_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st,
+                   static_cast<bf16_t*>(f1), p->b1, chunks, d_ff);
+        BPT_HIP(hipGetLastError());
+    }
+    if ((rc = gemm(bl, rows, d, d_ff, f1, false, p->W2, false, acc2, true))) return rc;
     BPT_LAUNCH("residual_layer_norm_kernel", residual_layer_norm_kernel, dim3(ln_blocks), dim3(256), 0, st,
                static_cast<const bf16_t*>(z), acc2, p->b2, p->g2, p->beta2, static_cast<bf16_t*>(Y), st2, rows, d, eps);
     BPT_HIP(hipGetLastError());
@@ -721,6 +880,7 @@ int bpt_layer_bwd(const bpt_graph_t* g, int32_t B, int32_t H, float scale, const
     hipStream_t st = static_cast<hipStream_t>(stream);
     rocblas_handle h = blas_handle(g->device);
     if (!h || rocblas_set_stream(h, st) != rocblas_status_success) return BPT_ERR_LAUNCH;
+    const Blas bl = {h, g->device, st};
     const unsigned char* fw = static_cast<const unsigned char*>(fwd_workspace);
     unsigned char* ws = static_cast<unsigned char*>(workspace);
     const bf16_t* qkvo = reinterpret_cast<const bf16_t*>(fw + F.qkvo);
@@ -749,14 +909,14 @@ int bpt_layer_bwd(const bpt_graph_t* g, int32_t B, int32_t H, float scale, const
     // FFN: dW2 = F^T dS2, dH = (dS2 W2^T) where the hidden unit was active, db1, dW1 = Z^T dH
     if ((rc = gemm_at_b_sliced(h, d_ff, d, rows, f1, ds2, d, gw, pick_slices(d, d_ff, rows), d, gr->dW2, nullptr, nullptr, st)))
         return rc;
-    if ((rc = gemm_rm(h, rows, d_ff, d, ds2, false, p->W2, true, dh, false))) return rc;
+    if ((rc = gemm(bl, rows, d_ff, d, ds2, false, p->W2, true, dh, false))) return rc;
     const int relu_blocks = (int)std::min<int64_t>(kColumnSumBlocks, rows);
     BPT_LAUNCH("relu_bwd_kernel", relu_bwd_kernel, dim3(relu_blocks), dim3(256), 0, st, dh, f1, part, rows, d_ff);
     BPT_HIP(hipGetLastError());
     if ((rc = column_sum(part, relu_blocks, d_ff, d_ff, gr->db1, nullptr, nullptr, st))) return rc;
     if ((rc = gemm_at_b_sliced(h, d, d_ff, rows, z, dh, d_ff, gw, pick_slices(d, d_ff, rows), d_ff, gr->dW1, nullptr, nullptr, st)))
         return rc;
-    if ((rc = gemm_rm(h, rows, d, d_ff, dh, false, p->W1, true, t, true))) return rc;
+    if ((rc = gemm(bl, rows, d, d_ff, dh, false, p->W1, true, t, true))) return rc;
     // first normalisation with dZ = dS2 + dH W1^T: dS1 (= the gradient of X's residual branch and of the
     // attention sublayer's output), dg1, dbeta1 (the third column sum, that of dS1, belongs to no parameter)
     if ((rc = launch_ln_bwd(d, ln_blocks, st, static_cast<const bf16_t*>(ds2), static_cast<const float*>(t), Xb, acc1,
@@ -767,7 +927,7 @@ int bpt_layer_bwd(const bpt_graph_t* g, int32_t B, int32_t H, float scale, const
     // attention sublayer: dWo = O^T dS1, dO = dS1 Wo^T, then the attention's own backward
     if ((rc = gemm_at_b_sliced(h, d, d, rows, o, ds1, d, gw, pick_slices(d, d, rows), d, gr->dWo, nullptr, nullptr, st, 4 * d)))
         return rc;
-    if ((rc = gemm_rm(h, rows, d, d, ds1, false, p->Wo, true, da, false, 0.f, 0, 4 * d))) return rc;
+    if ((rc = gemm(bl, rows, d, d, ds1, false, p->Wo, true, da, false, 0, 4 * d))) return rc;
     // dQ, dK, dV leave the attention's backward rounded to bf16, side by side next to dO: no cast pass
     if ((rc = bpt_attn_bwd(g, &s, q, k, v, rel, lse, da, dqkvo, dqkvo + d, dqkvo + 2 * d, d_rel, ws + L.attn, attn_ws, stream)))
         return rc;
@@ -776,7 +936,7 @@ int bpt_layer_bwd(const bpt_graph_t* g, int32_t B, int32_t H, float scale, const
     if ((rc = gemm_at_b_sliced(h, d, 3 * d, rows, X, dqkvo, 4 * d, gw, pick_slices(d, 3 * d, rows), d, gr->dWq, gr->dWk, gr->dWv,
                                st)))
         return rc;
-    if ((rc = gemm_rm(h, rows, d, 3 * d, dqkvo, false, wqkv, true, t, true, 0.f, 4 * d))) return rc;
+    if ((rc = gemm(bl, rows, d, 3 * d, dqkvo, false, wqkv, true, t, true, 4 * d))) return rc;
     BPT_LAUNCH("add_cast_kernel", add_cast_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st,
                static_cast<const bf16_t*>(ds1), static_cast<const float*>(t), static_cast<bf16_t*>(dX), chunks);
     BPT_HIP(hipGetLastError());
