@@ -88,6 +88,10 @@ def parse():
                          "keep (the default leaves them unwritten, bpt_shape_t.leave_unkept)")
     ap.add_argument("--bf16-grads", action="store_true",
                     help="dQ, dK, dV rounded to bf16 by the backward (bpt_shape_t.grad_dtype) instead of fp32")
+    ap.add_argument("--memory", choices=("heads", "nodes", "qkvo"), default="heads",
+                    help="heads: tensors in [B][H][N][D] memory; nodes: [B][N][H][D], what a projection of node rows writes; "
+                         "qkvo: rows of [Q | K | V | out][H][D] and [dQ | dK | dV | dout][H][D], the graph layer's buffers "
+                         "(gradients bf16)")
     ap.add_argument("--packed", action="store_true",
                     help="workloads with sequences of different lengths: one graph for the whole batch with rows only for "
                          "the nodes that exist (bpt_build_batch_graph) instead of the padded trees")
@@ -361,12 +365,26 @@ def main():
         edge_inst = w.H * sum(bpt.bpt_count_edges(w.n, w.k, w.causal, int(x)) for x in lengths)
 
     Q, K, V, R, dO = dev["Q"], dev["K"], dev["V"], dev["Rel"], dev["dO"]
-    out = torch.empty_like(Q)
+    out = None
+    if args.memory == "nodes":   # the same values, the heads of a node side by side in memory
+        Q, K, V, dO = (t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) for t in (Q, K, V, dO))
+    elif args.memory == "qkvo":
+        args.bf16_grads = True
+        rows = torch.empty((w.B, Q.shape[2], 4, w.H, w.D), dtype=tdt, device="cuda")
+        grows = torch.empty_like(rows)
+        for slot, t in enumerate((Q, K, V)):
+            rows[:, :, slot] = t.permute(0, 2, 1, 3)
+        grows[:, :, 3] = dO.permute(0, 2, 1, 3)
+        Q, K, V, out = (rows[:, :, slot].permute(0, 2, 1, 3) for slot in range(4))
+        dO = grows[:, :, 3].permute(0, 2, 1, 3)
+    if out is None:
+        out = torch.empty_like(Q)
     lse = torch.empty(Q.shape[:3], dtype=torch.float32, device="cuda")
     if args.bf16_grads and w.dtype != "bf16":
         sys.exit("--bf16-grads is for the bf16 workloads")
     gdt = torch.bfloat16 if args.bf16_grads else torch.float32
-    grads = tuple(torch.empty(Q.shape, dtype=gdt, device="cuda") for _ in range(3)) + (
+    grads = (tuple(grows[:, :, slot].permute(0, 2, 1, 3) for slot in range(3)) if args.memory == "qkvo" else
+             tuple(torch.empty_like(Q, dtype=gdt) for _ in range(3))) + (
         torch.empty(R.shape, dtype=torch.float32, device="cuda"),)
     fws, bws = bpt.workspace_bytes(g, Q, w.scale)
     ws_f = torch.empty(max(fws, 256), dtype=torch.uint8, device="cuda")
@@ -502,7 +520,7 @@ def main():
     # measured HBM traffic (rocprofv3 counters, profiles/hbm_traffic.txt) -- only if taken on these kernel sources
     per_kernel, measured_on = measured_traffic(w.name)
     sources = kernel_source_hash()
-    fresh = bool(per_kernel) and measured_on == sources and args.dropout == 0 and not args.bf16_grads
+    fresh = bool(per_kernel) and measured_on == sources and args.dropout == 0 and not args.bf16_grads and args.memory == "heads"
     traffic = step_traffic = None
     if fresh:
         if dominant in per_kernel:
@@ -523,7 +541,7 @@ def main():
         "traffic_source": ("profiles/hbm_traffic.txt" if fresh else
                            "none for this workload" if not per_kernel else
                            "stale: profiles/hbm_traffic.txt was taken on kernel sources %s, these are %s" % (measured_on, sources)
-                           if measured_on != sources else "not measured with dropout"),
+                           if measured_on != sources else "not measured with these options"),
         "launch_ms": round(kernel_ms[dominant], 4),
         "limiter": "latency of the chain row gather -> LDS -> matrix products -> exp -> matrix products inside a "
                    "wavefront at two wavefronts per SIMD (counters in profiles/): neither HBM nor the matrix cores are "
@@ -592,7 +610,8 @@ def main():
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "n": w.n, "k": w.k, "causal": w.causal, "batch": w.B, "heads": w.H,
                    "head_dim": w.D, "nodes": g.num_nodes, "edges": g.num_edges, "edge_instances": edge_inst,
-                   "backward": w.backward, "dropout": args.dropout, "gradients": "bf16" if args.bf16_grads else "fp32", "unkept_rows": ("unwritten" if leave else "zero-filled") if lengths is not None else None,
+                   "backward": w.backward, "dropout": args.dropout, "gradients": "bf16" if args.bf16_grads else "fp32",
+                   "memory": {"heads": "[B][H][N][D]", "nodes": "[B][N][H][D]", "qkvo": "[B][N][Q|K|V|out][H][D]"}[args.memory], "unkept_rows": ("unwritten" if leave else "zero-filled") if lengths is not None else None,
                    "lengths": ([int(v) for v in lengths] if lengths is not None else None)},
         "graph_build_ms": round(build_ms, 3),
         "edges_per_s_incl_build": round(edge_inst / ((ms_per_step + build_ms) * 1e-3), 1),
