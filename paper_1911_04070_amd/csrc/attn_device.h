@@ -348,6 +348,10 @@ __device__ __forceinline__ void store_once(float4* p, float4 v) {
     typedef float vec4 __attribute__((ext_vector_type(4)));
     __builtin_nontemporal_store(vec4{v.x, v.y, v.z, v.w}, reinterpret_cast<vec4*>(p));
 }
+__device__ __forceinline__ void store_once(uint4* p, uint4 v) {
+    typedef uint32_t vec4 __attribute__((ext_vector_type(4)));
+    __builtin_nontemporal_store(vec4{v.x, v.y, v.z, v.w}, reinterpret_cast<vec4*>(p));
+}
 // Gradient rows (dQ, dK, dV) leave as fp32 or, on request, rounded to bf16 (round to nearest even): `tensor` is
 // the caller's pointer, `elem` an element offset (strides count elements of either type), and with as_bf16 the
 // pointer addresses bf16 elements.  as_bf16 is the same in all lanes.

@@ -183,6 +183,11 @@ __global__ void __launch_bounds__(kTileThreads) fwd_span_tile_kernel(const SpanA
         d[3] = make_uint2(v1.z, v1.w);
     }
     wave_lds_sync();
+    // V^T operands of all three groups; v_s is then free to carry the finished rows on their way out
+    bf16x8_t vB[4];
+#pragma unroll
+    for (int f = 0; f < 4; ++f) vB[f] = lds_transposed_b(v_s, kVStride, f, g, j);
+    const int r8 = lane >> 3, piece = lane & 7;
 
 #pragma unroll
     for (int grp = 0; grp < 3; ++grp) {
@@ -237,26 +242,34 @@ __global__ void __launch_bounds__(kTileThreads) fwd_span_tile_kernel(const SpanA
 #pragma unroll
         for (int f = 0; f < 4; ++f) {
             o[f] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-            o[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pA, lds_transposed_b(v_s, kVStride, f, g, j), o[f], 0, 0, 0);
+            o[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vB[f], pA, o[f], 0, 0, 0);
         }
-        // C[m = query][n = feature]: this lane holds queries 4g..4g+3, feature 16f + j
+        // out^T = V^T P^T (the operands of P V changed places, the registers are the same), C[m = feature][n = query]:
+        // this lane holds features 16f + 4g .. + 3 of query j
         if (grp < 2) {
             // l == 0: a span past the end of a shorter sequence, its row is zero
             constexpr bool guard = PACKED;
             const int lse_row = PACKED ? node + __shfl(dvec, level) : node;   // (all lanes take part in the exchange)
             if (g == 0 && valid && !(guard && l <= 0.f))
                 a.lse[span_lse_at<PACKED>(a, bh) + lse_row] = l > 0.f ? (m + fast_log2(l)) * kLn2 : 0.f;
+            // the rows go through v_s and leave whole, 16 bytes per lane: eight rows of 128 contiguous bytes per store
+            const float inv = l > 0.f ? 1.f / l : 0.f;
+            wave_lds_sync();   // the previous group's rows have been read
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int slot = 4 * g + r;
+            for (int f = 0; f < 4; ++f)
+                *reinterpret_cast<uint2*>(v_s + j * kVStride + 16 * f + 4 * g) =
+                    make_uint2(pack_bf16(o[f][0] * inv, o[f][1] * inv), pack_bf16(o[f][2] * inv, o[f][3] * inv));
+            wave_lds_sync();
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int slot = 8 * h + r8;
                 const float lq = __shfl(l, slot);
                 const int orow_at = span_slot_row<PACKED>(a, grp, slot, t0, dvec);
                 if (grp == 1 && slot == 15) continue;
                 if (guard && lq <= 0.f) continue;   // a span past the end of the sequence has no row
-                bf16_t* orow = a.out + base + (int64_t)orow_at * a.sn + j;
-                const float inv = lq > 0.f ? 1.f / lq : 0.f;
-#pragma unroll
-                for (int f = 0; f < 4; ++f) store_once(&orow[16 * f], (bf16_t)to_bf16_bits(o[f][r] * inv));
+                const uint2* src = reinterpret_cast<const uint2*>(v_s + slot * kVStride + piece * 8);
+                const uint2 x0 = src[0], x1 = src[1];
+                store_once(reinterpret_cast<uint4*>(a.out + base + (int64_t)orow_at * a.sn + piece * 8), make_uint4(x0.x, x0.y, x1.x, x1.y));
             }
         } else {
             // partial of the ancestor at level 6 + slot: [bh][level][block][66]
@@ -265,13 +278,12 @@ __global__ void __launch_bounds__(kTileThreads) fwd_span_tile_kernel(const SpanA
                 dst[64] = m;
                 dst[65] = l;
             }
+            if (j < nanc) {   // (a partial is 264 bytes: 8-byte stores)
+                float* dst = a.part + (((int64_t)bh * nanc + j) * nblk + blk) * kPartStride + 4 * g;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int slot = 4 * g + r;
-                if (slot < nanc) {
-                    float* dst = a.part + (((int64_t)bh * nanc + slot) * nblk + blk) * kPartStride + j;
-#pragma unroll
-                    for (int f = 0; f < 4; ++f) dst[16 * f] = o[f][r];
+                for (int f = 0; f < 4; ++f) {
+                    *reinterpret_cast<float2*>(dst + 16 * f) = make_float2(o[f][0], o[f][1]);
+                    *reinterpret_cast<float2*>(dst + 16 * f + 2) = make_float2(o[f][2], o[f][3]);
                 }
             }
         }
@@ -485,6 +497,7 @@ __global__ void __launch_bounds__(kTileThreads, 3) bwd_q_span_tile_kernel(const 
     bf16x8_t kB[4];
 #pragma unroll
     for (int f = 0; f < 4; ++f) kB[f] = lds_transposed_b(k_s, kVStride, f, g, j);
+    const int r8 = lane >> 3, piece = lane & 7;   // k_s is free from here on: it carries the finished rows on their way out
 
 #pragma unroll
     for (int grp = 0; grp < 3; ++grp) {
@@ -530,33 +543,48 @@ __global__ void __launch_bounds__(kTileThreads, 3) bwd_q_span_tile_kernel(const 
 #pragma unroll
             for (int f = 0; f < 4; ++f) {
                 dq[f] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-                dq[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sH, kB[f], dq[f], 0, 0, 0);
-                dq[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sL, kB[f], dq[f], 0, 0, 0);
+                // transposed (the operands changed places): this lane holds features 16f + 4g .. + 3 of query j
+                dq[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kB[f], sH, dq[f], 0, 0, 0);
+                dq[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kB[f], sL, dq[f], 0, 0, 0);
             }
             if (g == 0 && valid)
                 a.stat[(int64_t)bh * a.N + node] = make_float2((((t0 >> level) + loc) << level) < len ? lse2 : kLseGone, dl);
             constexpr bool guard = PACKED;   // packed batch: a span past the end of the sequence has no row
+            // the rows go through k_s and leave whole, 16 bytes per lane
+            wave_lds_sync();   // the previous group's rows have been read
             if (G16) {
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int slot = 4 * g + r;
+                for (int f = 0; f < 4; ++f)
+                    *reinterpret_cast<uint2*>(k_s + j * kVStride + 16 * f + 4 * g) =
+                        make_uint2(pack_bf16(a.scale * dq[f][0], a.scale * dq[f][1]), pack_bf16(a.scale * dq[f][2], a.scale * dq[f][3]));
+                wave_lds_sync();
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int slot = 8 * h + r8;
                     const int row = span_slot_row<PACKED>(a, grp, slot, t0, dvec);
                     if (grp == 1 && slot == 15) continue;
                     if (guard && !span_slot_kept(a, grp, slot, t0, len)) continue;
-                    bf16_t* orow = reinterpret_cast<bf16_t*>(a.dQ) + base + (int64_t)row * a.sn + j;
-#pragma unroll
-                    for (int f = 0; f < 4; ++f) store_once(&orow[16 * f], (bf16_t)to_bf16_bits(a.scale * dq[f][r]));
+                    const uint2* src = reinterpret_cast<const uint2*>(k_s + slot * kVStride + piece * 8);
+                    const uint2 x0 = src[0], x1 = src[1];
+                    store_once(reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(a.dQ) + base + (int64_t)row * a.sn + piece * 8),
+                               make_uint4(x0.x, x0.y, x1.x, x1.y));
                 }
             } else {
+                float* stage = reinterpret_cast<float*>(k_s);   // [16 queries][kDqStride]: exactly the 32 staged K rows
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int slot = 4 * g + r;
+                for (int f = 0; f < 4; ++f) {
+                    const f32x4_t x = {a.scale * dq[f][0], a.scale * dq[f][1], a.scale * dq[f][2], a.scale * dq[f][3]};
+                    *reinterpret_cast<f32x4_t*>(stage + j * kDqStride + 16 * f + 4 * g) = x;
+                }
+                wave_lds_sync();
+#pragma unroll
+                for (int h = 0; h < 4; ++h) {
+                    const int slot = 4 * h + g;
                     const int row = span_slot_row<PACKED>(a, grp, slot, t0, dvec);
                     if (grp == 1 && slot == 15) continue;
                     if (guard && !span_slot_kept(a, grp, slot, t0, len)) continue;
-                    float* orow = a.dQ + base + (int64_t)row * a.sn + j;
-#pragma unroll
-                    for (int f = 0; f < 4; ++f) store_once(&orow[16 * f], a.scale * dq[f][r]);
+                    store_once(reinterpret_cast<float4*>(a.dQ + base + (int64_t)row * a.sn + 4 * j),
+                               *reinterpret_cast<const float4*>(stage + slot * kDqStride + 4 * j));
                 }
             }
         } else {
@@ -576,22 +604,18 @@ __global__ void __launch_bounds__(kTileThreads, 3) bwd_q_span_tile_kernel(const 
 #pragma unroll
             for (int f = 0; f < 4; ++f) {
                 ow[f] = op[f] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-                ow[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wH, kB[f], ow[f], 0, 0, 0);
-                ow[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wL, kB[f], ow[f], 0, 0, 0);
-                op[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pH, kB[f], op[f], 0, 0, 0);
-                op[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pL, kB[f], op[f], 0, 0, 0);
+                ow[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kB[f], wH, ow[f], 0, 0, 0);   // transposed as well
+                ow[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kB[f], wL, ow[f], 0, 0, 0);
+                op[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kB[f], pH, op[f], 0, 0, 0);
+                op[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kB[f], pL, op[f], 0, 0, 0);
             }
             if (g == 0 && valid) a.part[(((int64_t)bh * nanc + j) * nblk + blk) * kQPartStride + 2 * kD] = dl;
+            if (j < nanc) {   // features 16f + 4g .. + 3 of ancestor j: 16 bytes at a time
+                float* dst = a.part + (((int64_t)bh * nanc + j) * nblk + blk) * kQPartStride + 4 * g;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int slot = 4 * g + r;
-                if (slot < nanc) {
-                    float* dst = a.part + (((int64_t)bh * nanc + slot) * nblk + blk) * kQPartStride + j;
-#pragma unroll
-                    for (int f = 0; f < 4; ++f) {
-                        dst[16 * f] = ow[f][r];
-                        dst[kD + 16 * f] = op[f][r];
-                    }
+                for (int f = 0; f < 4; ++f) {
+                    *reinterpret_cast<f32x4_t*>(dst + 16 * f) = ow[f];
+                    *reinterpret_cast<f32x4_t*>(dst + kD + 16 * f) = op[f];
                 }
             }
         }

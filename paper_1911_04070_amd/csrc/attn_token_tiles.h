@@ -30,6 +30,7 @@ constexpr int kTileWaves = kTileThreads / 64;
 constexpr int kRelStride = 72;   // bf16 per LDS row of the compact table (64 + padding: 144 B)
 constexpr int kVStride = 68;     // bf16 per LDS row of a staged V row (136 B)
 constexpr int kRowStride = 72;   // bf16 per LDS row where rows are written and read 16 bytes at a time (144 B)
+constexpr int kDqStride = 68;    // floats per row of a tile's fp32 dQ rows on their way out through LDS (16 rows fit the K row buffer)
 
 constexpr int kDenseChunks = 8;   // 16-id chunks the dense variant of bwd_q_tile_kernel keeps d_rel sums for
 struct TileArgs {
@@ -459,13 +460,11 @@ __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArg
                 for (int r = 0; r < 4; ++r)
                     sc[c][r] *= drop_scale(rowh, (uint32_t)relid_s[max(cid[c][r], 0)], a.drop_thr, a.drop_inv_keep);
         }
-        // the accumulators hold tokens 4g..4g+3: fetch their correction factors
+        // the accumulators hold out^T, C[m = feature][n = token]: all four values of a lane belong to its token j
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const float cr4 = __shfl(corr, 4 * g + r);
+        for (int f = 0; f < 4; ++f)
 #pragma unroll
-            for (int f = 0; f < 4; ++f) o[f][r] *= cr4;
-        }
+            for (int r = 0; r < 4; ++r) o[f][r] *= corr;
         u32x4 pa;
         pa.x = pack_bf16(sc[0][0], sc[0][1]);
         pa.y = pack_bf16(sc[0][2], sc[0][3]);
@@ -474,7 +473,7 @@ __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArg
         const bf16x8_t pA = __builtin_bit_cast(bf16x8_t, pa);
 #pragma unroll
         for (int f = 0; f < 4; ++f)
-            o[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pA, lds_transposed_b(v_s, kRowStride, f, g, j), o[f], 0, 0, 0);
+            o[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lds_transposed_b(v_s, kRowStride, f, g, j), pA, o[f], 0, 0, 0);
 
         if (cc.pair == cc.npairs - 1) {   // the tile is complete
             const int64_t base = (int64_t)(cc.bh / a.H) * a.sb + (int64_t)(cc.bh % a.H) * a.sh;
@@ -489,14 +488,25 @@ __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArg
             constexpr bool guard = PACKED;
             const int64_t lse_at = PACKED ? (int64_t)(cc.bh / a.H) * a.lse_sb + (int64_t)(cc.bh % a.H) * a.lse_sh : (int64_t)cc.bh * a.N;
             if (g == 0 && !(guard && t0 + j >= len)) a.lse[lse_at + row0 + j] = t0 + j < len ? (m_run + fast_log2(l)) * kLn2 : 0.f;
-            bf16_t* orow = a.out + base + (int64_t)row0 * a.sn + j;
+            // out^T = V^T P^T (the operands of P V changed places: the same registers): lane (g, j) holds features
+            // 16f + 4g .. + 3 of token j.  The rows go through k_s (this pair's products have read it; the next
+            // pair's rows are written behind the barrier at the top of the loop) and leave as whole rows, 16 bytes
+            // per lane: a store instruction writes eight rows of 128 contiguous bytes.
+            const float inv = t0 + j < len ? 1.f / l : 0.f;
+            wave_lds_sync();
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const float inv = t0 + 4 * g + r < len ? 1.f / __shfl(l, 4 * g + r) : 0.f;
-                if (guard && t0 + 4 * g + r >= len) continue;
+            for (int f = 0; f < 4; ++f) {
+                const u32x2 w = {pack_bf16(o[f][0] * inv, o[f][1] * inv), pack_bf16(o[f][2] * inv, o[f][3] * inv)};
+                *reinterpret_cast<u32x2*>(k_s + j * kRowStride + 16 * f + 4 * g) = w;
+            }
+            wave_lds_sync();
+            bf16_t* orow = a.out + base + (int64_t)row0 * a.sn + piece * 8;
 #pragma unroll
-                for (int f = 0; f < 4; ++f)
-                    store_once(&orow[(int64_t)(4 * g + r) * a.sn + 16 * f], (bf16_t)to_bf16_bits(o[f][r] * inv));
+            for (int h = 0; h < 2; ++h) {
+                const int row = 8 * h + r8;
+                if (guard && t0 + row >= len) continue;
+                store_once(reinterpret_cast<uint4*>(orow + (int64_t)row * a.sn),
+                           *reinterpret_cast<const uint4*>(k_s + row * kRowStride + piece * 8));
             }
         }
         cc = cr;
@@ -861,10 +871,12 @@ __global__ void __launch_bounds__(kTileThreads, DENSE ? 1 : 2) bwd_q_tile_kernel
 #pragma unroll
         for (int f = 0; f < 4; ++f) {
             const bf16x8_t kB = lds_transposed_b(k_s, kRowStride, f, g, j);
-            ow[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wH, kB, ow[f], 0, 0, 0);
-            ow[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wL, kB, ow[f], 0, 0, 0);
-            op[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pH, kB, op[f], 0, 0, 0);
-            op[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pL, kB, op[f], 0, 0, 0);
+            // transposed, C[m = feature][n = token] (the operands of W K changed places, the registers are the same):
+            // all values of a lane belong to its token j, and a lane holds 4 consecutive features of the row
+            ow[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kB, wH, ow[f], 0, 0, 0);
+            ow[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kB, wL, ow[f], 0, 0, 0);
+            op[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kB, pH, op[f], 0, 0, 0);
+            op[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kB, pL, op[f], 0, 0, 0);
         }
         if (cc.pair == cc.npairs - 1) {   // the tile is complete
             const int64_t base = (int64_t)(cc.bh / a.H) * a.sb + (int64_t)(cc.bh % a.H) * a.sh;
@@ -902,8 +914,8 @@ __global__ void __launch_bounds__(kTileThreads, DENSE ? 1 : 2) bwd_q_tile_kernel
 #pragma unroll
                     for (int f = 0; f < 4; ++f) {
                         const bf16x8_t rB = lds_tr8(rel_s, kRelStride, ks + 8 * g, 16 * f, j);
-                        dqr[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aH, rB, dqr[f], 0, 0, 0);
-                        dqr[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aL, rB, dqr[f], 0, 0, 0);
+                        dqr[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(rB, aH, dqr[f], 0, 0, 0);   // transposed as well
+                        dqr[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(rB, aL, dqr[f], 0, 0, 0);
                     }
                 }
                 // d_rel += dS^T [ids][16 tokens] x Q [16 tokens][features], 16 ids at a time: the A operand is one
@@ -928,31 +940,37 @@ __global__ void __launch_bounds__(kTileThreads, DENSE ? 1 : 2) bwd_q_tile_kernel
                     }
                 wave_lds_sync();   // before the next tile clears the tables and forms its bias table
             }
-            // packed batch: the sequence's token rows begin at row level_delta(.., 0); a row past its end is not stored
-            const int64_t qrow_out = base + (int64_t)(PACKED ? t0 + level_delta(cc.dvec, 0) : t0) * a.sn + j;
+            // dQ rows of the tile, lane (g, j): features 16f + 4g .. + 3 of token j.  They go through the row buffers
+            // (free until the next pair is staged behind the barrier at the top of the loop) and leave as whole rows,
+            // 16 bytes per lane: a store instruction writes four rows of 256 (fp32) or eight of 128 (bf16) contiguous
+            // bytes.  Packed batch: the sequence's token rows begin at row level_delta(.., 0); a row past its end is
+            // not stored.
+            const int64_t qrow_out = base + (int64_t)(PACKED ? t0 + level_delta(cc.dvec, 0) : t0) * a.sn;
             const int live = PACKED ? len - t0 : 16;   // rows of the tile that may be stored
-            float dr[4];
+            if (j < live) {
+                if (a.grad_bf16) {
+                    bf16_t* dst = reinterpret_cast<bf16_t*>(a.dQ) + qrow_out + (int64_t)j * a.sn + 4 * g;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) dr[r] = __shfl(delta, 4 * g + r);
-            if (a.grad_bf16) {   // one branch around all stores of the tile
-                bf16_t* dst = reinterpret_cast<bf16_t*>(a.dQ) + qrow_out;
+                    for (int f = 0; f < 4; ++f) {
+                        float x[4];
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    if (4 * g + r < live) {
-#pragma unroll
-                        for (int f = 0; f < 4; ++f)
-                            store_once(&dst[(int64_t)(4 * g + r) * a.sn + 16 * f],
-                                       (bf16_t)to_bf16_bits(a.scale * (ow[f][r] - dr[r] * op[f][r] + dqr[f][r])));
+                        for (int r = 0; r < 4; ++r) x[r] = a.scale * (ow[f][r] - delta * op[f][r] + dqr[f][r]);
+                        typedef uint32_t vec2 __attribute__((ext_vector_type(2)));
+                        const vec2 w = {pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3])};
+                        __builtin_nontemporal_store(w, reinterpret_cast<vec2*>(dst + 16 * f));
                     }
-            } else {
-                float* dst = a.dQ + qrow_out;
+                } else {
+                    float* dst = a.dQ + qrow_out + (int64_t)j * a.sn + 4 * g;
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    if (4 * g + r < live) {
-#pragma unroll
-                        for (int f = 0; f < 4; ++f)
-                            store_once(&dst[(int64_t)(4 * g + r) * a.sn + 16 * f], a.scale * (ow[f][r] - dr[r] * op[f][r] + dqr[f][r]));
+                    for (int f = 0; f < 4; ++f) {
+                        float4 x;
+                        x.x = a.scale * (ow[f][0] - delta * op[f][0] + dqr[f][0]);
+                        x.y = a.scale * (ow[f][1] - delta * op[f][1] + dqr[f][1]);
+                        x.z = a.scale * (ow[f][2] - delta * op[f][2] + dqr[f][2]);
+                        x.w = a.scale * (ow[f][3] - delta * op[f][3] + dqr[f][3]);
+                        store_once(reinterpret_cast<float4*>(dst + 16 * f), x);
                     }
+                }
             }
         }
         cc = cr;
