@@ -371,6 +371,14 @@ __device__ __forceinline__ void store_grad4(float* tensor, int64_t elem, float4 
         store_once(reinterpret_cast<float4*>(tensor + elem), v);
     }
 }
+__device__ __forceinline__ float4 load_grad4(const float* tensor, int64_t elem, bool as_bf16) {
+    if (as_bf16) {
+        const uint2 w = *reinterpret_cast<const uint2*>(reinterpret_cast<const bf16_t*>(tensor) + elem);
+        return make_float4(__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xFFFF0000u), __uint_as_float(w.y << 16),
+                           __uint_as_float(w.y & 0xFFFF0000u));
+    }
+    return *reinterpret_cast<const float4*>(tensor + elem);
+}
 __device__ __forceinline__ float load_grad(const float* tensor, int64_t elem, bool as_bf16) {
     return as_bf16 ? __uint_as_float((uint32_t)reinterpret_cast<const bf16_t*>(tensor)[elem] << 16) : tensor[elem];
 }

@@ -988,7 +988,8 @@ __global__ void __launch_bounds__(kTileThreads, DENSE ? 1 : 2) bwd_q_tile_kernel
 // so an edge needs no search for its row and no lookup of its id.  Q rows are staged
 // row-major and enter the products through transposing LDS reads:
 //   d_rel[id][f] += DS^T (A, 16-byte rows) x Q (B, transposed read),
-//   dQ[row][f]   += scale * DS (A, transposed read of DS^T) x Rel (B, transposed read).
+//   dQ[row][f]   += scale * DS x Rel, formed transposed (Rel^T DS^T, both operands transposed reads) so that a
+//                   lane adds to 16 contiguous bytes of a row.
 // Wavefront w owns id chunks w and w + 8; its accumulators live across the blocks the
 // workgroup walks and are written once, as this workgroup's copy, in compact-id order.
 struct RelGradArgs {
@@ -1127,13 +1128,11 @@ __global__ void __launch_bounds__(kThreads, CPW == 2 ? 4 : 2) rel_grad_tile_kern
         }
         // the dQ values this thread will add to, and everything the next block needs
         const int mc = wave >> 2, fc = wave & 3;
-        float dq_old[4];
+        // (the product below is formed transposed, C[m = feature][n = row]: a lane holds features 16fc + 4g .. + 3 of row j)
         const int live = PACKED ? seq_length_u(a.seq_len, bh / a.H, a.n) : a.n, tok0 = PACKED ? a.delta[bh / a.H] : 0;
-#pragma unroll
-        for (int m = 0; m < 4; ++m) {
-            const int row = row0 + 16 * mc + 4 * g + m;
-            dq_old[m] = row < live ? load_grad(a.dQ, base + (int64_t)(row + tok0) * a.sn + 16 * fc + j, a.grad_bf16) : 0.f;
-        }
+        const int dq_row = row0 + 16 * mc + j;
+        const int64_t dq_at = base + (int64_t)(dq_row + tok0) * a.sn + 16 * fc + 4 * g;
+        const float4 dq_old = dq_row < live ? load_grad4(a.dQ, dq_at, a.grad_bf16) : make_float4(0.f, 0.f, 0.f, 0.f);
         const int blk_next = next_block(blk + gridDim.x);
         if (blk_next < total) prefetch(blk_next);
         __syncthreads();
@@ -1141,14 +1140,13 @@ __global__ void __launch_bounds__(kThreads, CPW == 2 ? 4 : 2) rel_grad_tile_kern
             f32x4_t dq = {0.f, 0.f, 0.f, 0.f};
             for (int ks = 0; ks < nids; ks += 32) {
                 const bf16x8_t rb = lds_tr8(rel_s, kRelStride, ks + 8 * g, 16 * fc, j);
-                dq = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lds_tr8(ds_hi, kRgStride, ks + 8 * g, 16 * mc, j), rb, dq, 0, 0, 0);
-                dq = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lds_tr8(ds_lo, kRgStride, ks + 8 * g, 16 * mc, j), rb, dq, 0, 0, 0);
+                dq = __builtin_amdgcn_mfma_f32_16x16x32_bf16(rb, lds_tr8(ds_hi, kRgStride, ks + 8 * g, 16 * mc, j), dq, 0, 0, 0);
+                dq = __builtin_amdgcn_mfma_f32_16x16x32_bf16(rb, lds_tr8(ds_lo, kRgStride, ks + 8 * g, 16 * mc, j), dq, 0, 0, 0);
             }
-#pragma unroll
-            for (int m = 0; m < 4; ++m) {
-                const int row = row0 + 16 * mc + 4 * g + m;
-                if (row < live) store_grad(a.dQ, base + (int64_t)(row + tok0) * a.sn + 16 * fc + j, dq_old[m] + a.scale * dq[m], a.grad_bf16);
-            }
+            if (dq_row < live)
+                store_grad4(a.dQ, dq_at,
+                            make_float4(dq_old.x + a.scale * dq[0], dq_old.y + a.scale * dq[1], dq_old.z + a.scale * dq[2],
+                                        dq_old.w + a.scale * dq[3]), a.grad_bf16);
         }
         bf16x8_t qb[4];
 #pragma unroll
