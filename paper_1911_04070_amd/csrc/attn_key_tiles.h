@@ -304,24 +304,25 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyA
 #pragma unroll
             for (int f = 0; f < 4; ++f) {
                 const bf16x8_t qB = lds_transposed_b(q_s, kRowStride, f, g, j), gB = lds_transposed_b(g_s, kRowStride, f, g, j);
-                dk[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sH, qB, dk[f], 0, 0, 0);
-                dk[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sL, qB, dk[f], 0, 0, 0);
-                dv[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pH, gB, dv[f], 0, 0, 0);
-                dv[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pL, gB, dv[f], 0, 0, 0);
+                // transposed, C[m = feature][n = key] (the operands of dS^T Q changed places, the registers are the
+                // same): a lane holds features 16f + 4g .. + 3 of key j
+                dk[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qB, sH, dk[f], 0, 0, 0);
+                dk[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qB, sL, dk[f], 0, 0, 0);
+                dv[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(gB, pH, dv[f], 0, 0, 0);
+                dv[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(gB, pL, dv[f], 0, 0, 0);
             }
         }
-        // C[m = key][n = feature]: lane holds keys 4g..4g+3, feature 16f + j.  Stored from there, a
-        // wavefront instruction would write 4-byte pieces of 4 rows; the sums go through LDS (the
-        // row buffers are free now) and leave as 16 bytes per lane, rows of 512 contiguous bytes.
+        // Stored from the registers, a wavefront instruction would write 64-byte pieces of 16 rows (measured: the key
+        // side 21 % slower than with whole lines); the sums go through LDS (the row buffers are free now), 16 bytes
+        // per lane in and out, and leave as rows of 256 contiguous bytes.
         wave_lds_sync();   // the last pair's reads of q_s, g_s are done
         float* o_s = reinterpret_cast<float*>(q_s);   // [16 keys][kKvOutStride]: 64 dK | 64 dV
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-#pragma unroll
-            for (int f = 0; f < 4; ++f) {
-                o_s[(4 * g + r) * kKvOutStride + 16 * f + j] = a.scale * dk[f][r];
-                o_s[(4 * g + r) * kKvOutStride + kD + 16 * f + j] = dv[f][r];
-            }
+        for (int f = 0; f < 4; ++f) {
+            const f32x4_t xk = {a.scale * dk[f][0], a.scale * dk[f][1], a.scale * dk[f][2], a.scale * dk[f][3]};
+            *reinterpret_cast<f32x4_t*>(o_s + j * kKvOutStride + 16 * f + 4 * g) = xk;
+            *reinterpret_cast<f32x4_t*>(o_s + j * kKvOutStride + kD + 16 * f + 4 * g) = dv[f];
+        }
         wave_lds_sync();
         if (part < 0 && a.grad_bf16) {   // rounded to bf16: 8 bytes per lane
 #pragma unroll
@@ -603,22 +604,22 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_chain_kernel(const Key
 #pragma unroll
             for (int f = 0; f < 4; ++f) {
                 const bf16x8_t qB = lds_transposed_b(q_s, kRowStride, f, g, j), gB = lds_transposed_b(g_s, kRowStride, f, g, j);
-                dk[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sH, qB, dk[f], 0, 0, 0);
-                dk[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sL, qB, dk[f], 0, 0, 0);
-                dv[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pH, gB, dv[f], 0, 0, 0);
-                dv[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pL, gB, dv[f], 0, 0, 0);
+                // transposed, C[m = feature][n = key] (the operands of dS^T Q changed places, the registers are the
+                // same): a lane holds features 16f + 4g .. + 3 of key j
+                dk[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qB, sH, dk[f], 0, 0, 0);
+                dk[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qB, sL, dk[f], 0, 0, 0);
+                dv[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(gB, pH, dv[f], 0, 0, 0);
+                dv[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(gB, pL, dv[f], 0, 0, 0);
             }
             if (c2 + 2 == tile_end) {   // wave-uniform: the tile is complete
-                // C[m = key][n = feature]: lane holds keys 4g..4g+3, feature 16f + j.  o_s was read (if at all) at
-                // the top of this iteration, before a barrier of the wavefront
+                // o_s was read (if at all) at the top of this iteration, before a barrier of the wavefront
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
-#pragma unroll
-                    for (int f = 0; f < 4; ++f) {
-                        o_s[(4 * g + r) * kKvOutStride + 16 * f + j] = a.scale * dk[f][r];
-                        o_s[(4 * g + r) * kKvOutStride + kD + 16 * f + j] = dv[f][r];
-                        dk[f][r] = dv[f][r] = 0.f;
-                    }
+                for (int f = 0; f < 4; ++f) {
+                    const f32x4_t xk = {a.scale * dk[f][0], a.scale * dk[f][1], a.scale * dk[f][2], a.scale * dk[f][3]};
+                    *reinterpret_cast<f32x4_t*>(o_s + j * kKvOutStride + 16 * f + 4 * g) = xk;
+                    *reinterpret_cast<f32x4_t*>(o_s + j * kKvOutStride + kD + 16 * f + 4 * g) = dv[f];
+                    dk[f] = dv[f] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                }
                 staged = true;
                 st_node0 = node0 + dlev;
                 // (packed batch: keys the sequence does not keep have no row; partial sums keep all of the tile's keys)
