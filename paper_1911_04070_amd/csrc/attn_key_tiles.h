@@ -126,16 +126,16 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyA
         // rows can be requested (its column ids and map words); the rows of pair i+1 are
         // requested in the middle of pair i, as soon as the registers of pair i's rows are free,
         // and the ids of pair i+2 right after, so the gathers overlap the second products.
-        int node[2][2];   // [chunk][half]: query node whose row this lane helps to fetch
+        // the 32 query nodes of a pair arrive with one instruction, node l in lane l (and l + 32); the lane that
+        // fetches a piece of row 16 ci + 8 h + r8 reads its id from there, and lane l fetches (lse, delta) of node l
+        int colv;
         uint2 mpn[2];
         auto load_idx = [&](int c2) {   // a pair past the end repeats the last one (valid addresses, results unused)
             const int cc = c0 + min(c2, nch - 2);
+            colv = buf_i32(rC, (cc * 16 + (lane & 31)) * 4);
 #pragma unroll
             for (int ci = 0; ci < 2; ++ci) {
-                const int at = (cc + ci) * 16;
-                node[ci][0] = buf_i32(rC, (at + r8) * 4);
-                node[ci][1] = buf_i32(rC, (at + 8 + r8) * 4);
-                const u32x2 m2 = __builtin_amdgcn_raw_buffer_load_b64(rM, (at + j) * 32 + 8 * g, 0, 0);
+                const u32x2 m2 = __builtin_amdgcn_raw_buffer_load_b64(rM, ((cc + ci) * 16 + j) * 32 + 8 * g, 0, 0);
                 mpn[ci] = make_uint2(m2.x, m2.y);
             }
         };
@@ -143,21 +143,22 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyA
         // instruction fetches 8 whole rows (two per 16-row chunk).  The rows go through LDS to get
         // into the operand layouts of the matrix instructions.
         Row<bf16_t> qa[2][2], ga[2][2];
-        float2 stn[2][2];   // (lse, delta) of the row, kept by the lane that fetches its first piece
-        uint32_t rhn[2][2];  // DROP: the row's hash
+        float2 stn;         // (lse, delta) of query node `lane % 32` of the pair
+        uint32_t rhn = 0;   // DROP: its hash
         const uint32_t bhh = DROP ? drop_bh_hash(a.drop_seed, bh) : 0u;
         auto load_rows = [&]() {
 #pragma unroll
             for (int ci = 0; ci < 2; ++ci)
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
-                    const int row = PACKED ? packed_row(node[ci][h], a.num_levels - 1, dvec) : node[ci][h];
+                    const int node = __shfl(colv, 16 * ci + 8 * h + r8);
+                    const int row = PACKED ? packed_row(node, a.num_levels - 1, dvec) : node;
                     const int off = (int)__umul24(row, a.row_bytes) + piece * 16;
                     buf_row(rQ, off, qa[ci][h]);
                     buf_row(rG, off, ga[ci][h]);
-                    stn[ci][h] = buf_f2(rS, node[ci][h] * 8);
-                    if (DROP) rhn[ci][h] = drop_row_hash(bhh, node[ci][h]);
                 }
+            stn = buf_f2(rS, colv * 8);
+            if (DROP) rhn = drop_row_hash(bhh, colv);
         };
         load_idx(0);
 
@@ -203,9 +204,9 @@ __global__ void __launch_bounds__(kTileThreads, 2) bwd_kv_tile_kernel(const KeyA
                     const int row = 16 * ci + 8 * h + r8;
                     *reinterpret_cast<uint4*>(q_s + row * kRowStride + piece * 8) = qa[ci][h].w;
                     *reinterpret_cast<uint4*>(g_s + row * kRowStride + piece * 8) = ga[ci][h].w;
-                    if (piece == 0) stat_s[row] = stn[ci][h];
-                    if (DROP && piece == 0) rowh_s[row] = rhn[ci][h];
                 }
+            if (lane < 32) stat_s[lane] = stn;
+            if (DROP && lane < 32) rowh_s[lane] = rhn;
             __builtin_amdgcn_sched_barrier(0);
             // the row registers are free: request the next pair's rows, then the ids of the pair after it
             const uint2 mpc[2] = {mp[0], mp[1]};
