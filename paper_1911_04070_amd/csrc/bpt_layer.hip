@@ -450,7 +450,7 @@ int gemm_rm(rocblas_handle h, int64_t M, int64_t N, int64_t K, const void* A, bo
 // stream capture.  A product hipBLASLt has no algorithm for reports false and the caller takes the rocBLAS path.
 struct LtPlan {
     int64_t M, N, K, lda, ldc;
-    bool ta, tb, c_fp32, bias_relu;
+    bool ta, tb, c_fp32, bias_relu, add;
     hipblasLtMatmulDesc_t desc;
     hipblasLtMatrixLayout_t la, lb, lc;
     hipblasLtMatmulAlgo_t algo;
@@ -478,23 +478,24 @@ LtContext* lt_context(int device) {
     }
     return &c;
 }
-// C[M][N] = op(A) op(B) (+ bias[N], then max(0, .) with bias_relu), arguments as gemm_rm's with beta = 0
+// C[M][N] = op(A) op(B) (+ bias[N], then max(0, .) with bias_relu; + add[M][N], of C's type and row stride, with add:
+// the sum is formed in fp32 and rounded once), arguments as gemm_rm's with beta = 0
 bool gemm_lt(int device, hipStream_t st, int64_t M, int64_t N, int64_t K, const void* A, bool ta, const void* B, bool tb, void* C,
-             bool c_fp32, int64_t lda, int64_t ldc, const float* bias_relu) {
+             bool c_fp32, int64_t lda, int64_t ldc, const float* bias_relu, const void* add) {
     LtContext* c = lt_context(device);
     if (!c) return false;
     const int64_t lda_ = lda ? lda : (ta ? M : K), ldc_ = ldc ? ldc : N;
     LtPlan* plan = nullptr;
     for (LtPlan& q : c->plans)
         if (q.M == M && q.N == N && q.K == K && q.lda == lda_ && q.ldc == ldc_ && q.ta == ta && q.tb == tb && q.c_fp32 == c_fp32 &&
-            q.bias_relu == (bias_relu != nullptr)) {
+            q.bias_relu == (bias_relu != nullptr) && q.add == (add != nullptr)) {
             plan = &q;
             break;
         }
     if (!plan) {
         hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
         if (hipStreamIsCapturing(st, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) return false;
-        LtPlan q = {M, N, K, lda_, ldc_, ta, tb, c_fp32, bias_relu != nullptr, nullptr, nullptr, nullptr, nullptr, {}, 0};
+        LtPlan q = {M, N, K, lda_, ldc_, ta, tb, c_fp32, bias_relu != nullptr, add != nullptr, nullptr, nullptr, nullptr, nullptr, {}, 0};
         // column-major view: C^T [N x M] = op(B)^T [N x K] op(A)^T [K x M] on the same buffers
         const hipblasOperation_t op_first = tb ? HIPBLAS_OP_T : HIPBLAS_OP_N, op_second = ta ? HIPBLAS_OP_T : HIPBLAS_OP_N;
         const hipDataType ctype = c_fp32 ? HIP_R_32F : HIP_R_16BF;
@@ -525,7 +526,8 @@ bool gemm_lt(int device, hipStream_t st, int64_t M, int64_t N, int64_t K, const 
         float best_ms = 0.f;
         hipEvent_t e0 = nullptr, e1 = nullptr;
         if (ok && found > 1 && (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)) found = 1;
-        const float one = 1.f, zero = 0.f;
+        const float one = 1.f, beta = add ? 1.f : 0.f;
+        const void* cin = add ? add : C;
         for (int i = 0; ok && i < found; ++i) {
             if (res[i].state != HIPBLAS_STATUS_SUCCESS || res[i].workspaceSize > kLtWorkspace) continue;
             if (found == 1) {
@@ -535,7 +537,7 @@ bool gemm_lt(int device, hipStream_t st, int64_t M, int64_t N, int64_t K, const 
             bool ran = true;
             for (int rep = 0; rep < kLtTimedRuns + 1 && ran; ++rep) {   // the first run is not timed
                 if (rep == 1) ran = hipEventRecord(e0, st) == hipSuccess;
-                ran = ran && hipblasLtMatmul(c->handle, q.desc, &one, B, q.la, A, q.lb, &zero, C, q.lc, C, q.lc, &res[i].algo, c->ws,
+                ran = ran && hipblasLtMatmul(c->handle, q.desc, &one, B, q.la, A, q.lb, &beta, cin, q.lc, C, q.lc, &res[i].algo, c->ws,
                                              kLtWorkspace, st) == HIPBLAS_STATUS_SUCCESS;
             }
             float ms = 0.f;
@@ -566,9 +568,9 @@ bool gemm_lt(int device, hipStream_t st, int64_t M, int64_t N, int64_t K, const 
     if (bias_relu && hipblasLtMatmulDescSetAttribute(plan->desc, HIPBLASLT_MATMUL_DESC_BIAS_POINTER, &bias_relu, sizeof(bias_relu)) !=
                          HIPBLAS_STATUS_SUCCESS)
         return false;
-    const float one = 1.f, zero = 0.f;
-    return hipblasLtMatmul(c->handle, plan->desc, &one, B, plan->la, A, plan->lb, &zero, C, plan->lc, C, plan->lc, &plan->algo, c->ws,
-                           kLtWorkspace, st) == HIPBLAS_STATUS_SUCCESS;
+    const float one = 1.f, beta = add ? 1.f : 0.f;
+    return hipblasLtMatmul(c->handle, plan->desc, &one, B, plan->la, A, plan->lb, &beta, add ? add : C, plan->lc, C, plan->lc,
+                           &plan->algo, c->ws, kLtWorkspace, st) == HIPBLAS_STATUS_SUCCESS;
 }
 
 // the dense products of the layer: hipBLASLt where it has an algorithm (always, with the bias + ReLU epilogue or
@@ -589,11 +591,16 @@ bool lt_enabled() {
 int gemm(const Blas& b, int64_t M, int64_t N, int64_t K, const void* A, bool ta, const void* B, bool tb, void* C, bool c_fp32,
          int64_t lda = 0, int64_t ldc = 0, const float* bias_relu = nullptr, bool* fused = nullptr) {
     if (fused) *fused = false;
-    if (lt_enabled() && gemm_lt(b.device, b.st, M, N, K, A, ta, B, tb, C, c_fp32, lda, ldc, bias_relu)) {
+    if (lt_enabled() && gemm_lt(b.device, b.st, M, N, K, A, ta, B, tb, C, c_fp32, lda, ldc, bias_relu, nullptr)) {
         if (fused) *fused = true;
         return BPT_OK;
     }
     return gemm_rm(b.h, M, N, K, A, ta, B, tb, C, c_fp32, 0.f, lda, ldc);
+}
+// C (bf16) = add (bf16) + op(A) op(B) in one product where hipBLASLt has it; else false and nothing is written
+bool gemm_add(const Blas& b, int64_t M, int64_t N, int64_t K, const void* A, bool ta, const void* B, bool tb, void* C,
+              const void* add, int64_t lda = 0) {
+    return lt_enabled() && gemm_lt(b.device, b.st, M, N, K, A, ta, B, tb, C, false, lda, 0, nullptr, add);
 }
 
 size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -916,10 +923,15 @@ int bpt_layer_bwd(const bpt_graph_t* g, int32_t B, int32_t H, float scale, const
     if ((rc = column_sum(part, relu_blocks, d_ff, d_ff, gr->db1, nullptr, nullptr, st))) return rc;
     if ((rc = gemm_at_b_sliced(h, d, d_ff, rows, z, dh, d_ff, gw, pick_slices(d, d_ff, rows), d_ff, gr->dW1, nullptr, nullptr, st)))
         return rc;
-    if ((rc = gemm(bl, rows, d, d_ff, dh, false, p->W1, true, t, true))) return rc;
     // first normalisation with dZ = dS2 + dH W1^T: dS1 (= the gradient of X's residual branch and of the
-    // attention sublayer's output), dg1, dbeta1 (the third column sum, that of dS1, belongs to no parameter)
-    if ((rc = launch_ln_bwd(d, ln_blocks, st, static_cast<const bf16_t*>(ds2), static_cast<const float*>(t), Xb, acc1,
+    // attention sublayer's output), dg1, dbeta1 (the third column sum, that of dS1, belongs to no parameter).
+    // dZ is one product with dS2 as its addend (bf16, in the first half of t); without hipBLASLt the product
+    // stays fp32 and the kernel adds
+    bf16_t* dz = reinterpret_cast<bf16_t*>(t);
+    const bool dz_joined = gemm_add(bl, rows, d, d_ff, dh, false, p->W1, true, dz, ds2);
+    if (!dz_joined && (rc = gemm(bl, rows, d, d_ff, dh, false, p->W1, true, t, true))) return rc;
+    if ((rc = launch_ln_bwd(d, ln_blocks, st, dz_joined ? static_cast<const bf16_t*>(dz) : static_cast<const bf16_t*>(ds2),
+                            dz_joined ? static_cast<const float*>(nullptr) : static_cast<const float*>(t), Xb, acc1,
                             static_cast<const float*>(nullptr), p->g1, st1, ds1, part, rows, d,
                             static_cast<const int32_t*>(nullptr), g->num_nodes, lg)))
         return rc;
@@ -936,6 +948,8 @@ int bpt_layer_bwd(const bpt_graph_t* g, int32_t B, int32_t H, float scale, const
     if ((rc = gemm_at_b_sliced(h, d, 3 * d, rows, X, dqkvo, 4 * d, gw, pick_slices(d, 3 * d, rows), d, gr->dWq, gr->dWk, gr->dWv,
                                st)))
         return rc;
+    // (the residual branch's gradient dS1 enters as the product's addend: one rounding, no pass of its own)
+    if (gemm_add(bl, rows, d, 3 * d, dqkvo, false, wqkv, true, dX, ds1, 4 * d)) return BPT_OK;
     if ((rc = gemm(bl, rows, d, 3 * d, dqkvo, false, wqkv, true, t, true, 4 * d))) return rc;
     BPT_LAUNCH("add_cast_kernel", add_cast_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st,
                static_cast<const bf16_t*>(ds1), static_cast<const float*>(t), static_cast<bf16_t*>(dX), chunks);
