@@ -122,7 +122,10 @@ __device__ __forceinline__ int load_delta(const int32_t* delta, int nbatch, int 
     return lane < levels ? delta[lane * nbatch + b] : 0;
 }
 // the row of node `id` (any lane-varying id); dvec as loaded by load_delta
-__device__ __forceinline__ int packed_row(int id, int lg, int dvec) { return id + __shfl(dvec, node_level(id, lg)); }
+// (ds_bpermute takes the byte address of the source lane's value; a level is below 64, so no wrap-around is needed)
+__device__ __forceinline__ int packed_row(int id, int lg, int dvec) {
+    return id + __builtin_amdgcn_ds_bpermute(node_level(id, lg) << 2, dvec);
+}
 // delta of a level that is the same in all lanes
 __device__ __forceinline__ int level_delta(int dvec, int level) {
     return __builtin_amdgcn_readlane(dvec, __builtin_amdgcn_readfirstlane(level));
