@@ -191,6 +191,18 @@ struct TileCursor {
     int dvec;   // packed batch: this lane's delta of the sequence the tile belongs to (0 otherwise)
     bool valid;
 };
+// Says that everything but dvec is the same in all lanes.  With a lane's own dvec among the fields the compiler keeps
+// the whole cursor in vector registers, and what follows from it -- the divisions by the number of heads and by the
+// tiles per sequence, the tensors' base offsets: some hundred instructions per pair of chunks -- is done per lane.
+__device__ __forceinline__ void cursor_uniform(TileCursor& c) {
+    c.t = __builtin_amdgcn_readfirstlane(c.t);
+    c.pair = __builtin_amdgcn_readfirstlane(c.pair);
+    c.npairs = __builtin_amdgcn_readfirstlane(c.npairs);
+    c.cp0 = __builtin_amdgcn_readfirstlane(c.cp0);
+    c.bh = __builtin_amdgcn_readfirstlane(c.bh);
+    c.tile = __builtin_amdgcn_readfirstlane(c.tile);
+    c.valid = __builtin_amdgcn_readfirstlane((int)c.valid) != 0;
+}
 
 // REL_LDS: the compact relative-position table is staged in LDS; otherwise (large tables) its rows
 // are read from memory when a tile forms its bias table.
@@ -267,10 +279,15 @@ __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArg
         c.pair = 0;
         c.npairs = 1;
         c.dvec = 0;
+        if (PACKED) c.t = __builtin_amdgcn_readfirstlane(c.t);   // (see cursor_uniform)
         if (compact) {   // the next tile that exists; the walk covers nothing else
             const int idx = c.t * kTileWaves + wave;
             if (c.t < w.t_end && idx < live_total) {
                 nth_tile(pref_s, nbatch, a.H, a.num_tiles, false, idx, c.bh, c.tile);
+                if (PACKED) {
+                    c.bh = __builtin_amdgcn_readfirstlane(c.bh);
+                    c.tile = __builtin_amdgcn_readfirstlane(c.tile);
+                }
                 c.cp0 = a.chunk_ptr[c.tile];
                 c.npairs = (a.chunk_ptr[c.tile + 1] - c.cp0) >> 1;
                 c.dvec = PACKED ? load_delta(a.delta, nbatch, c.bh / a.H, lane, a.levels) : 0;
@@ -340,11 +357,13 @@ __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArg
     cc.t = w.t;
     enter_tile(cc);
     if (!cc.valid) return;
+    if (PACKED) cursor_uniform(cc);
     load_idx(cc);
     request_rows(cc);
     uint2 mp[2] = {mp_n[0], mp_n[1]};
     cr = cc;
     advance(cr);
+    if (PACKED) cursor_uniform(cr);
     if (cr.valid) load_idx(cr);
     ci = cr;
     advance(ci);
@@ -355,6 +374,11 @@ __global__ void __launch_bounds__(kTileThreads, 2) fwd_tile_kernel(const TileArg
     uint32_t rowh = 0;   // DROP: hash of (seed, batch*head, token j of the tile)
 
     while (cc.valid) {
+        if (PACKED) {
+            cursor_uniform(cc);
+            cursor_uniform(cr);
+            cursor_uniform(ci);
+        }
         if (cc.pair == 0) {   // a new tile: its Q rows arrived with the rows of this pair
             if (DROP) rowh = drop_row_hash(drop_bh_hash(a.drop_seed, cc.bh), cc.tile * 16 + j);
             qb0 = qn0;
@@ -614,10 +638,15 @@ __global__ void __launch_bounds__(kTileThreads, DENSE ? 1 : 2) bwd_q_tile_kernel
         c.pair = 0;
         c.npairs = 1;
         c.dvec = 0;
+        if (PACKED) c.t = __builtin_amdgcn_readfirstlane(c.t);   // (see cursor_uniform)
         if (compact) {   // the next tile that exists; the walk covers nothing else
             const int idx = c.t * kTileWaves + wave;
             if (c.t < w.t_end && idx < live_total) {
                 nth_tile(pref_s, nbatch, a.H, a.num_tiles, false, idx, c.bh, c.tile);
+                if (PACKED) {
+                    c.bh = __builtin_amdgcn_readfirstlane(c.bh);
+                    c.tile = __builtin_amdgcn_readfirstlane(c.tile);
+                }
                 c.cp0 = uniform_i32(a.chunk_ptr, c.tile);
                 c.npairs = (uniform_i32(a.chunk_ptr, c.tile + 1) - c.cp0) >> 1;
                 c.dvec = PACKED ? load_delta(a.delta, nbatch, c.bh / a.H, lane, a.levels) : 0;
@@ -730,11 +759,13 @@ __global__ void __launch_bounds__(kTileThreads, DENSE ? 1 : 2) bwd_q_tile_kernel
         write_drel();
         return;
     }
+    if (PACKED) cursor_uniform(cc);
     load_idx(cc);
     request_rows(cc);
     uint2 mp[2] = {mp_n[0], mp_n[1]};
     cr = cc;
     advance(cr);
+    if (PACKED) cursor_uniform(cr);
     if (cr.valid) load_idx(cr);
     ci = cr;
     advance(ci);
@@ -747,6 +778,11 @@ __global__ void __launch_bounds__(kTileThreads, DENSE ? 1 : 2) bwd_q_tile_kernel
     bool tables_clear = false;   // DENSE: the (w, p) table holds zeros
 
     while (cc.valid) {
+        if (PACKED) {
+            cursor_uniform(cc);
+            cursor_uniform(cr);
+            cursor_uniform(ci);
+        }
         if (cc.pair == 0) {   // a new tile: its operands arrived with the rows of this pair
             if (DROP) rowh = drop_row_hash(drop_bh_hash(a.drop_seed, cc.bh), cc.tile * 16 + j);
             qb0 = qn0; qb1 = qn1; gb0 = gn0; gb1 = gn1;
