@@ -581,12 +581,9 @@ struct Blas {
     int device;
     hipStream_t st;
 };
-bool lt_enabled() {
-    static const bool on = [] {
-        const char* e = getenv("BPT_LAYER_BLAS");
-        return !(e && std::string(e) == "rocblas");
-    }();
-    return on;
+bool lt_enabled() {   // read at every call: a process can compare the two paths
+    const char* e = getenv("BPT_LAYER_BLAS");
+    return !(e && std::string(e) == "rocblas");
 }
 int gemm(const Blas& b, int64_t M, int64_t N, int64_t K, const void* A, bool ta, const void* B, bool tb, void* C, bool c_fp32,
          int64_t lda = 0, int64_t ldc = 0, const float* bias_relu = nullptr, bool* fused = nullptr) {

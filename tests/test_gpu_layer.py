@@ -149,6 +149,53 @@ def test_layer_backward(n, k, causal, B, heads, d_ff, lengths, decisive):
     g.destroy()
 
 
+def test_layer_on_either_gemm_library(monkeypatch):
+    # The dense products run in hipBLASLt (bias + ReLU and the residual adds of the backward in the products' epilogues)
+    # or, with BPT_LAYER_BLAS=rocblas, in rocBLAS with the library's own bias + ReLU and add kernels: the fallback for
+    # a product hipBLASLt has no algorithm for.  Both against the oracle, forward and backward, and against each other.
+    import os
+    n, k, causal, B, heads, d_ff = 256, 4, True, 2, 2, 256
+    X, Rel, p = make_case(n, k, causal, B, heads, d_ff, 911, False)
+    p["b1"] = np.where(np.arange(d_ff) % 2 == 0, 6.0, -6.0).astype(np.float32)   # decided gates (see above)
+    rng = np.random.Generator(np.random.PCG64(912))
+    dY = round_to_bf16(rng.standard_normal(X.shape).astype(np.float32))[0]
+    g = bpt.bpt_build_graph(n, k, causal)
+    fws, bws = bpt.layer_workspace_bytes(g, B, heads, d_ff)
+    Xd, Rd, pd = torch.from_numpy(X).to(torch.bfloat16).cuda(), torch.from_numpy(Rel).to(torch.bfloat16).cuda(), to_dev(p)
+    dYd = torch.from_numpy(dY).to(torch.bfloat16).cuda()
+    ref_y = layer_forward(n, k, causal, heads, X, Rel, p, 0.125)
+    ref = layer_backward(n, k, causal, heads, X, Rel, p, dY, 0.125)
+    results = {}
+    for lib in ("hipblaslt", "rocblas"):
+        monkeypatch.setenv("BPT_LAYER_BLAS", lib)
+        assert os.environ["BPT_LAYER_BLAS"] == lib
+        ws_f = torch.empty(fws + 256, dtype=torch.uint8, device="cuda")
+        ws_b = torch.empty(bws + 256, dtype=torch.uint8, device="cuda")
+        bpt.bpt_profile_enable(True)
+        Y = bpt.bpt_layer_fwd(g, Xd, Rd, pd, heads, scale=0.125, workspace=ws_f)
+        dX, d_rel, grads = bpt.bpt_layer_bwd(g, Xd, Rd, pd, heads, ws_f, dYd, scale=0.125, workspace=ws_b)
+        torch.cuda.synchronize()
+        ran = set(bpt.bpt_profile_report())
+        bpt.bpt_profile_enable(False)
+        # the library's own bias + ReLU and add kernels run exactly when the products' epilogues do not do their work
+        assert ("bias_relu_kernel" in ran) == (lib == "rocblas"), ran
+        assert ("add_cast_kernel" in ran) == (lib == "rocblas"), ran
+        err = np.abs(Y.float().cpu().numpy().astype(np.float64) - ref_y).max()
+        assert err <= TOL, (lib, err)
+        got = {"dX": dX, "dRel": d_rel}
+        got.update(grads)
+        for name in ("dX", "dRel") + GRADS:
+            a = got[name].float().cpu().numpy().astype(np.float64)
+            v = float(np.abs(a - ref[name]).max()) / max(float(np.abs(ref[name]).max()), 1e-30)
+            assert np.isfinite(a).all() and v <= BWD_TOL_DECISIVE, (lib, name, v)
+        results[lib] = (Y.float().cpu().numpy(), dX.float().cpu().numpy())
+    # the two paths differ by roundings only (bias + ReLU on fp32 sums or on bf16 values, one or two roundings of dX)
+    assert np.abs(results["hipblaslt"][0] - results["rocblas"][0]).max() <= TOL
+    top = np.abs(results["rocblas"][1]).max()
+    assert np.abs(results["hipblaslt"][1] - results["rocblas"][1]).max() <= BWD_TOL_DECISIVE * top
+    g.destroy()
+
+
 @pytest.mark.parametrize("n,k,causal,heads,d_ff,lengths", [
     (256, 3, False, 4, 512, [256, 150, 31, 1]), (512, 4, True, 2, 256, [77, 512, 300]),
 ])
