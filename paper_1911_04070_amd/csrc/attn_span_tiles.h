@@ -372,20 +372,23 @@ __device__ __forceinline__ void fwd_span_merge_small(const SpanArgs& a, int item
     if (lane == 0) a.lse[span_lse_at<PACKED>(a, r.bh) + row] = ls > 0.f ? (mx + fast_log2(ls)) * kLn2 : 0.f;
 }
 
-// one kernel for both kinds of rows: the first `small_blocks` workgroups take 16 short rows each
-// (one per wavefront), the others one long row each
+// one kernel for both kinds of rows: the first workgroups take one long row each, the longest rows (the highest
+// levels) of all (batch, head)s first, so that they run while the short rows are handed out; the `small_blocks`
+// workgroups behind them take 16 short rows each (one per wavefront)
 template <bool PACKED>
 __global__ void __launch_bounds__(kSpanBigThreads) fwd_span_merge_kernel(const SpanArgs a, int first, int rows_small,
                                                                          int first_big, int rows_big, int small_blocks) {
     __shared__ float s_acc[64][kD + 4];
     __shared__ float s_l[64];
     __shared__ float s_m[kSpanBigThreads / 64];
-    if ((int)blockIdx.x < small_blocks) {   // uniform for the workgroup; this path has no barrier
-        fwd_span_merge_small<PACKED>(a, blockIdx.x * (kSpanBigThreads / 64) + (threadIdx.x >> 6), first, rows_small);
+    const int big_blocks = a.BH * rows_big;
+    if ((int)blockIdx.x >= big_blocks) {   // uniform for the workgroup; this path has no barrier
+        fwd_span_merge_small<PACKED>(a, (blockIdx.x - big_blocks) * (kSpanBigThreads / 64) + (threadIdx.x >> 6), first, rows_small);
         return;
     }
     SpanRow r;
-    if (!span_merge_row(a, blockIdx.x - small_blocks, first_big, rows_big, kPartStride, r)) return;   // uniform for the workgroup
+    const int big_item = (blockIdx.x % a.BH) * rows_big + (rows_big - 1 - blockIdx.x / a.BH);
+    if (!span_merge_row(a, big_item, first_big, rows_big, kPartStride, r)) return;   // uniform for the workgroup
     if (r.cnt == 0 && a.leave_unkept) return;
     const int t = threadIdx.x, fq = t & 15, pl = t >> 4;
     float mx = kNegBig;
@@ -657,12 +660,14 @@ __global__ void __launch_bounds__(kSpanBigThreads) bwd_q_span_merge_kernel(const
                                                                            int first_big, int rows_big, int small_blocks) {
     __shared__ float s_a[64][kD + 4], s_b[64][kD + 4];
     __shared__ float s_d[64];
-    if ((int)blockIdx.x < small_blocks) {
-        bwd_q_span_merge_small<PACKED>(a, blockIdx.x * (kSpanBigThreads / 64) + (threadIdx.x >> 6), first, rows_small);
+    const int big_blocks = a.BH * rows_big;
+    if ((int)blockIdx.x >= big_blocks) {
+        bwd_q_span_merge_small<PACKED>(a, (blockIdx.x - big_blocks) * (kSpanBigThreads / 64) + (threadIdx.x >> 6), first, rows_small);
         return;
     }
     SpanRow r;
-    if (!span_merge_row(a, blockIdx.x - small_blocks, first_big, rows_big, kQPartStride, r)) return;
+    const int big_item = (blockIdx.x % a.BH) * rows_big + (rows_big - 1 - blockIdx.x / a.BH);
+    if (!span_merge_row(a, big_item, first_big, rows_big, kQPartStride, r)) return;
     if (r.cnt == 0 && a.leave_unkept) {
         if (threadIdx.x == 0) a.stat[(int64_t)r.bh * a.N + r.v] = make_float2(kLseGone, 0.f);
         return;
